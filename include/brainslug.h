@@ -1,0 +1,255 @@
+/*
+ * brainslug.h -- C ABI of libbrainslug_hip: depth-first execution of a stack of
+ * consecutive non-convolution CNN layers on one AMD MI355X (gfx950).
+ *
+ * Method: BrainSlug (arXiv 1804.08378).  A "stack" is a run of consecutive
+ * optimizable layers (Section 3.2): element-wise layers (inference BatchNorm,
+ * ReLU, residual Add) and pooling layers (max, average).  Instead of executing
+ * the stack layer by layer through main memory (Figure 2), every tile of the
+ * activation is taken through all layers in registers / on-chip memory
+ * (Figure 3), so the tensor crosses HBM once in and once out.  The results are
+ * those of the layer-by-layer execution (Sections 1, 3, 6).
+ *
+ * Life cycle (Sections 4.1 "compile phase" and 4.2 "execution phase"):
+ *     bs_stack_create   layer list + input shape -> handle (host only)
+ *     bs_stack_plan     layers -> operations -> steps -> sequences -> tiles;
+ *                       uploads the folded BatchNorm parameters
+ *     bs_stack_run      enqueue the sequence kernels on a HIP stream
+ *     bs_stack_destroy
+ *
+ * Conventions
+ *   - Tensors are dense NCHW, float32 or bfloat16 (bs_dtype).  All tensors of one
+ *     stack share the dtype; BatchNorm parameters are always float32.
+ *   - "host" / "device" at each pointer says where the memory lives.  The caller
+ *     owns every buffer it passes; the library copies what it keeps.
+ *   - Every function returning bs_status returns BS_OK (0) on success and leaves
+ *     its outputs untouched on failure.  No function throws or aborts.
+ *   - A handle may be used from one thread at a time for create/plan/destroy;
+ *     bs_stack_run on a planned handle does not modify it and may be called
+ *     concurrently on different streams with different buffers.
+ */
+#ifndef BRAINSLUG_H
+#define BRAINSLUG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BS_API __attribute__((visibility("default")))
+
+#define BS_MAX_LAYERS 256      /* layers per stack                                  */
+#define BS_MAX_RESIDUALS 16    /* BS_ADD layers per stack                           */
+#define BS_MAX_INDEX_OUTPUTS 16 /* max-pool layers with return_indices per stack    */
+
+typedef enum bs_status {
+    BS_OK = 0,
+    BS_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+    BS_ERR_SHAPE = 2,       /* non-positive dimension, or a pooling output dimension < 1   */
+    BS_ERR_PARAM = 3,       /* k < 1, s < 1, p > k/2, var + eps <= 0, non-finite parameter */
+    BS_ERR_UNSUPPORTED = 4, /* ceil_mode, dilation != 1, unknown kind/dtype, too many layers */
+    BS_ERR_NOT_PLANNED = 5, /* run / info before a successful device plan                  */
+    BS_ERR_NO_FIT = 6,      /* a step does not fit the on-chip budget at the smallest tile */
+    BS_ERR_ALIGN = 7,       /* a device pointer is not 16-byte aligned                     */
+    BS_ERR_WORKSPACE = 8,   /* workspace missing or too small                              */
+    BS_ERR_HIP = 9,         /* a HIP call failed; see bs_last_hip_error()                  */
+    BS_ERR_ALLOC = 10,      /* host allocation failed                                      */
+    BS_ERR_RANGE = 11,      /* an index argument is out of range                           */
+    BS_ERR_ALIAS = 12       /* out overlaps an input where that is not allowed             */
+} bs_status;
+
+typedef enum bs_dtype { BS_F32 = 0, BS_BF16 = 1 } bs_dtype;
+
+typedef enum bs_layer_kind {
+    BS_BATCHNORM = 1, /* inference BatchNorm: y = (x - mean) / sqrt(var + eps) * gamma + beta  */
+    BS_RELU = 2,      /* y = x > 0 ? x : +0   (Section 2: f(x) = max(0, x))                    */
+    BS_ADD = 3,       /* y = x + r, r = the next residual tensor passed to bs_stack_run        */
+    BS_MAXPOOL = 4,   /* Section 2 pooling, maximum; optional argmax output                    */
+    BS_AVGPOOL = 5    /* Section 2 pooling, average (window sum, then normalisation; Listing 2) */
+} bs_layer_kind;
+
+/*
+ * One layer.  Unused fields must be zero.
+ *
+ * BS_BATCHNORM: gamma, beta, running_mean, running_var are HOST pointers to C
+ *   floats each (C = channels of the input shape); copied by bs_stack_create.
+ *   The library folds them once, in float64, into scale = gamma / sqrt(var + eps)
+ *   and shift = beta - mean * scale, each rounded once to float32, and evaluates
+ *   y = fma(x, scale, shift) in float32.
+ * BS_MAXPOOL / BS_AVGPOOL: window kh x kw, stride sh x sw, zero/ignored padding
+ *   ph x pw on each side (p <= k/2), floor output size H_out = (H + 2p - k) / s + 1.
+ *   Padding cells are never a maximum candidate and add nothing to an average.
+ *   Max: first maximum in row-major window order wins; with return_indices the
+ *   layer also yields int32 ih * W + iw of the winner in its own input plane.
+ *   Avg: float32 sum over the in-range cells in row-major order, multiplied by the
+ *   float32 reciprocal of kh * kw (count_include_pad != 0) or of the number of
+ *   in-range cells (count_include_pad == 0).
+ *   ceil_mode != 0 or a dilation other than 0 / 1 is rejected (BS_ERR_UNSUPPORTED).
+ */
+typedef struct bs_layer_desc {
+    int32_t kind; /* bs_layer_kind */
+    int32_t kh, kw, sh, sw, ph, pw;
+    int32_t count_include_pad;
+    int32_t return_indices;
+    int32_t ceil_mode;
+    int32_t dilation_h, dilation_w;
+    double eps;
+    const float *gamma;        /* host */
+    const float *beta;         /* host */
+    const float *running_mean; /* host */
+    const float *running_var;  /* host */
+} bs_layer_desc;
+
+typedef struct bs_stack bs_stack; /* opaque */
+
+/* Kernel families a sequence can be mapped to (Section 4.1, last paragraph: a
+ * single-step sequence streams values from operation to operation; a multi-step
+ * sequence keeps a cached buffer and synchronises between steps). */
+typedef enum bs_variant {
+    BS_VARIANT_AUTO = 0,
+    BS_VARIANT_STREAM = 1,      /* element-wise only: 128-bit streaming, registers only         */
+    BS_VARIANT_POOL_DIRECT = 2, /* one step, disjoint windows (k == s, p == 0): registers only   */
+    BS_VARIANT_LDS_TILE = 3     /* tiles with halos staged in LDS, ping-pong buffers, barriers   */
+} bs_variant;
+
+/*
+ * Planner options; NULL or all-zero = automatic.
+ *   max_lds_bytes           on-chip budget per work-group (Section 4.1 "resource limit")
+ *   max_steps_per_sequence  the strategy knob of Section 5.1 (1, 5, 0 = unrestricted)
+ *   threads_per_group       64..1024, multiple of 64 (0 = 256)
+ *   num_cus                 compute units to size grids for (0 = query the current device)
+ *   breadth_first           != 0: one sequence per layer, i.e. the layer-by-layer execution
+ *                           of Figure 2 with every intermediate in the workspace
+ *   force_variant           bs_variant to use wherever it is applicable (tests)
+ *   tile_rows, tile_cols, planes_per_group
+ *                           final-output tile of LDS sequences (0 = automatic)
+ *   host_only               != 0: plan without touching any device; such a plan can be
+ *                           inspected but bs_stack_run returns BS_ERR_NOT_PLANNED
+ */
+typedef struct bs_plan_options {
+    uint64_t max_lds_bytes;
+    int32_t max_steps_per_sequence;
+    int32_t threads_per_group;
+    int32_t num_cus;
+    int32_t breadth_first;
+    int32_t force_variant;
+    int32_t tile_rows, tile_cols, planes_per_group;
+    int32_t host_only;
+    int32_t reserved[5];
+} bs_plan_options;
+
+typedef struct bs_plan_info {
+    int32_t n_operations; /* layers mapped to basic operations (AvgPool = sum + normalisation) */
+    int32_t n_steps;
+    int32_t n_sequences;
+    int32_t device_planned;     /* 1 when bs_stack_run may be called                       */
+    uint64_t workspace_bytes;   /* device bytes bs_stack_run needs between sequences       */
+    uint64_t algorithmic_bytes; /* input + residuals + output (+ indices) of the whole stack */
+} bs_plan_info;
+
+typedef struct bs_step_info {
+    int32_t first_operation, n_operations; /* range in the operation list                  */
+    int32_t pool_operation;                /* index of its non-element-wise op, or -1      */
+    int32_t sequence;                      /* sequence it was put into                     */
+} bs_step_info;
+
+typedef struct bs_sequence_info {
+    int32_t first_step, n_steps;
+    int32_t first_layer, n_layers;
+    int32_t variant;                 /* bs_variant                                         */
+    int32_t n_levels;                /* pooling operations inside (LDS hand-offs + 1)      */
+    int32_t tile_rows, tile_cols;    /* final-output tile per work-group (LDS variant)     */
+    int32_t planes_per_group;
+    int32_t halo_rows, halo_cols;    /* input rows/cols an interior tile loads beyond tile*stride */
+    int32_t threads_per_group;
+    int64_t grid;                    /* work-groups                                        */
+    uint64_t lds_bytes;
+    int64_t in_shape[4], out_shape[4];
+    double redundancy;               /* elements loaded (with halos) / elements of the input */
+} bs_sequence_info;
+
+/* Names of the basic operations a plan lists (bs_stack_operation_name). */
+
+/*
+ * Create a stack from `n_layers` layer descriptions and the NCHW input shape
+ * (Section 4.3: the front-end hands the optimizer a run of optimizable layers
+ * with their parameters).  Pure host call; no device is touched.  `layers`,
+ * `in_shape` and every parameter array are read during the call only.
+ * Errors: BS_ERR_NULL, BS_ERR_SHAPE, BS_ERR_PARAM, BS_ERR_UNSUPPORTED, BS_ERR_ALLOC.
+ */
+BS_API bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers,
+                                 const int64_t in_shape[4], bs_dtype dtype, bs_stack **out);
+
+/* Free the handle, its host copies and its device parameter table.  NULL is allowed. */
+BS_API void bs_stack_destroy(bs_stack *stack);
+
+/* Output size of the stack (Section 4.2: the scheduler calculates the output
+ * size; the caller's framework allocates). */
+BS_API bs_status bs_stack_output_shape(const bs_stack *stack, int64_t out_shape[4]);
+/* Number of BS_ADD layers = residual tensors bs_stack_run expects (-1 if stack is NULL). */
+BS_API int32_t bs_stack_num_residuals(const bs_stack *stack);
+/* Shape residual tensor `i` must have (that of the i-th BS_ADD layer's input). */
+BS_API bs_status bs_stack_residual_shape(const bs_stack *stack, int32_t i, int64_t shape[4]);
+/* Number of max-pool layers with return_indices (-1 if stack is NULL). */
+BS_API int32_t bs_stack_num_index_outputs(const bs_stack *stack);
+/* Shape of index output `i` (the output shape of that max-pool layer), int32 elements. */
+BS_API bs_status bs_stack_index_shape(const bs_stack *stack, int32_t i, int64_t shape[4]);
+/* Folded BatchNorm parameters of layer `layer` (host float arrays of C elements, either may be
+ * NULL): what the kernels multiply and add.  BS_ERR_RANGE if that layer is not a BatchNorm. */
+BS_API bs_status bs_stack_folded_bn(const bs_stack *stack, int32_t layer, float *scale, float *shift);
+
+/*
+ * Plan the stack (Section 4.1, collapse process): map layers to operations, group
+ * operations into steps (any number of element-wise operations and at most one
+ * non-element-wise one per step), group steps into sequences that fit the on-chip
+ * budget, and choose kernel variant and tile geometry per sequence.  Unless
+ * opts->host_only is set it queries the current HIP device for limits that opts
+ * leaves at 0 and uploads the folded BatchNorm parameters (library-owned device
+ * memory, freed by bs_stack_destroy or a re-plan).  May be called again.
+ * Errors: BS_ERR_NULL, BS_ERR_PARAM (bad option), BS_ERR_NO_FIT, BS_ERR_HIP, BS_ERR_ALLOC.
+ */
+BS_API bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts);
+
+BS_API bs_status bs_stack_plan_info(const bs_stack *stack, bs_plan_info *info);
+BS_API bs_status bs_stack_step_info(const bs_stack *stack, int32_t step, bs_step_info *info);
+BS_API bs_status bs_stack_sequence_info(const bs_stack *stack, int32_t sequence, bs_sequence_info *info);
+/* Static name of operation `op` of the plan ("BatchNorm", "ReLU", "Add", "MaxPooling",
+ * "AvgPooling", "AvgNormalization"), or NULL when out of range / not planned. */
+BS_API const char *bs_stack_operation_name(const bs_stack *stack, int32_t op);
+/* Device bytes bs_stack_run needs as workspace (0 when the stack is one sequence). */
+BS_API uint64_t bs_stack_workspace_bytes(const bs_stack *stack);
+
+/*
+ * Enqueue the stack on `stream` (a hipStream_t passed as void*; NULL = the null
+ * stream) of the device the plan was made on.  Never synchronises, never
+ * allocates, returns as soon as the kernels are queued; sequences of one stack
+ * run one after the other (Section 4.2).
+ *   in         device, dense NCHW of the create-time shape and dtype
+ *   residuals  host array of bs_stack_num_residuals() DEVICE pointers, in layer
+ *              order (may be NULL when there are none)
+ *   out        device, bs_stack_output_shape() elements of the stack dtype.
+ *              Must not overlap any input, except that a stack without pooling
+ *              layers may run in place (out == in)
+ *   indices    host array of bs_stack_num_index_outputs() DEVICE int32 pointers;
+ *              the array or single entries may be NULL to skip those outputs
+ *   workspace  device, >= bs_stack_workspace_bytes() (NULL allowed when that is 0)
+ * All device pointers must be 16-byte aligned.
+ * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED, BS_ERR_ALIGN, BS_ERR_WORKSPACE,
+ *         BS_ERR_ALIAS, BS_ERR_HIP (launch failure; raw code in bs_last_hip_error()).
+ */
+BS_API bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,
+                              void *out, int32_t *const *indices, void *workspace,
+                              uint64_t workspace_bytes, void *stream);
+
+/* Static, never NULL. */
+BS_API const char *bs_status_string(bs_status status);
+BS_API const char *bs_version(void);
+/* Raw hipError_t of the calling thread's last failed HIP call inside the library (0 if none). */
+BS_API int32_t bs_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BRAINSLUG_H */

@@ -1,0 +1,363 @@
+"""ctypes binding of libbrainslug_hip.so -- argument marshalling only.
+
+Every function here has the name of the C entry point it forwards to
+(include/brainslug.h).  `Stack` is a small convenience wrapper around a
+handle that takes torch tensors and passes their device pointers and the
+current HIP stream.  No step of the method runs in Python, and there is no
+fallback: if the library has not been built, loading it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libbrainslug_hip.so")
+
+BS_OK = 0
+BS_F32, BS_BF16 = 0, 1
+BS_BATCHNORM, BS_RELU, BS_ADD, BS_MAXPOOL, BS_AVGPOOL = 1, 2, 3, 4, 5
+BS_VARIANT_AUTO, BS_VARIANT_STREAM, BS_VARIANT_POOL_DIRECT, BS_VARIANT_LDS_TILE = 0, 1, 2, 3
+VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile"}
+STATUS_NAMES = {
+    0: "BS_OK", 1: "BS_ERR_NULL", 2: "BS_ERR_SHAPE", 3: "BS_ERR_PARAM", 4: "BS_ERR_UNSUPPORTED",
+    5: "BS_ERR_NOT_PLANNED", 6: "BS_ERR_NO_FIT", 7: "BS_ERR_ALIGN", 8: "BS_ERR_WORKSPACE",
+    9: "BS_ERR_HIP", 10: "BS_ERR_ALLOC", 11: "BS_ERR_RANGE", 12: "BS_ERR_ALIAS",
+}
+
+_f32p = C.POINTER(C.c_float)
+
+
+class bs_layer_desc(C.Structure):
+    _fields_ = [("kind", C.c_int32),
+                ("kh", C.c_int32), ("kw", C.c_int32), ("sh", C.c_int32), ("sw", C.c_int32),
+                ("ph", C.c_int32), ("pw", C.c_int32),
+                ("count_include_pad", C.c_int32), ("return_indices", C.c_int32),
+                ("ceil_mode", C.c_int32), ("dilation_h", C.c_int32), ("dilation_w", C.c_int32),
+                ("eps", C.c_double),
+                ("gamma", _f32p), ("beta", _f32p), ("running_mean", _f32p), ("running_var", _f32p)]
+
+
+class bs_plan_options(C.Structure):
+    _fields_ = [("max_lds_bytes", C.c_uint64),
+                ("max_steps_per_sequence", C.c_int32), ("threads_per_group", C.c_int32),
+                ("num_cus", C.c_int32), ("breadth_first", C.c_int32), ("force_variant", C.c_int32),
+                ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("planes_per_group", C.c_int32),
+                ("host_only", C.c_int32), ("reserved", C.c_int32 * 5)]
+
+
+class bs_plan_info(C.Structure):
+    _fields_ = [("n_operations", C.c_int32), ("n_steps", C.c_int32), ("n_sequences", C.c_int32),
+                ("device_planned", C.c_int32), ("workspace_bytes", C.c_uint64),
+                ("algorithmic_bytes", C.c_uint64)]
+
+
+class bs_step_info(C.Structure):
+    _fields_ = [("first_operation", C.c_int32), ("n_operations", C.c_int32),
+                ("pool_operation", C.c_int32), ("sequence", C.c_int32)]
+
+
+class bs_sequence_info(C.Structure):
+    _fields_ = [("first_step", C.c_int32), ("n_steps", C.c_int32),
+                ("first_layer", C.c_int32), ("n_layers", C.c_int32),
+                ("variant", C.c_int32), ("n_levels", C.c_int32),
+                ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("planes_per_group", C.c_int32),
+                ("halo_rows", C.c_int32), ("halo_cols", C.c_int32), ("threads_per_group", C.c_int32),
+                ("grid", C.c_int64), ("lds_bytes", C.c_uint64),
+                ("in_shape", C.c_int64 * 4), ("out_shape", C.c_int64 * 4), ("redundancy", C.c_double)]
+
+
+_lib = None
+
+_SIGNATURES = {
+    "bs_stack_create": (C.c_int, [C.POINTER(bs_layer_desc), C.c_int32, C.POINTER(C.c_int64), C.c_int,
+                                  C.POINTER(C.c_void_p)]),
+    "bs_stack_destroy": (None, [C.c_void_p]),
+    "bs_stack_output_shape": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
+    "bs_stack_num_residuals": (C.c_int32, [C.c_void_p]),
+    "bs_stack_residual_shape": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64)]),
+    "bs_stack_num_index_outputs": (C.c_int32, [C.c_void_p]),
+    "bs_stack_index_shape": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int64)]),
+    "bs_stack_folded_bn": (C.c_int, [C.c_void_p, C.c_int32, _f32p, _f32p]),
+    "bs_stack_plan": (C.c_int, [C.c_void_p, C.POINTER(bs_plan_options)]),
+    "bs_stack_plan_info": (C.c_int, [C.c_void_p, C.POINTER(bs_plan_info)]),
+    "bs_stack_step_info": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(bs_step_info)]),
+    "bs_stack_sequence_info": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(bs_sequence_info)]),
+    "bs_stack_operation_name": (C.c_char_p, [C.c_void_p, C.c_int32]),
+    "bs_stack_workspace_bytes": (C.c_uint64, [C.c_void_p]),
+    "bs_stack_run": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
+                               C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_status_string": (C.c_char_p, [C.c_int]),
+    "bs_version": (C.c_char_p, []),
+    "bs_last_hip_error": (C.c_int32, []),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def load():
+    """Load the built library; raises (never falls back) when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "or `python paper_1804_08378_amd/build.py`")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+class BrainSlugError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        msg = load().bs_status_string(self.status).decode()
+        extra = ""
+        if self.status == 9:
+            extra = f" (hipError_t {load().bs_last_hip_error()})"
+        super().__init__(f"{where}: {STATUS_NAMES.get(self.status, self.status)}: {msg}{extra}")
+
+
+def _check(status: int, where: str):
+    if status != BS_OK:
+        raise BrainSlugError(status, where)
+
+
+# ---- same-name forwarding functions ---------------------------------------------------
+def bs_version() -> str:
+    return load().bs_version().decode()
+
+
+def bs_status_string(status: int) -> str:
+    return load().bs_status_string(int(status)).decode()
+
+
+def bs_last_hip_error() -> int:
+    return int(load().bs_last_hip_error())
+
+
+def _shape4(shape):
+    if len(shape) != 4:
+        raise ValueError("expected an NCHW shape")
+    return (C.c_int64 * 4)(*[int(v) for v in shape])
+
+
+def _marshal_layers(layers, channels):
+    """layer dicts (see workloads) -> (ctypes array, keep-alive list)."""
+    arr = (bs_layer_desc * max(1, len(layers)))()
+    keep = []
+    for i, l in enumerate(layers):
+        d = arr[i]
+        kind = l["kind"]
+        if kind == "bn":
+            d.kind = BS_BATCHNORM
+            d.eps = float(l["eps"])
+            for field, key in (("gamma", "gamma"), ("beta", "beta"), ("running_mean", "mean"),
+                               ("running_var", "var")):
+                a = np.ascontiguousarray(l[key], dtype=np.float32)
+                if a.size != channels:
+                    raise ValueError("BatchNorm parameter length must equal C")
+                keep.append(a)
+                setattr(d, field, a.ctypes.data_as(_f32p))
+        elif kind == "relu":
+            d.kind = BS_RELU
+        elif kind == "add":
+            d.kind = BS_ADD
+        elif kind in ("maxpool", "avgpool"):
+            d.kind = BS_MAXPOOL if kind == "maxpool" else BS_AVGPOOL
+            d.kh, d.kw = l["k"]
+            d.sh, d.sw = l["s"]
+            d.ph, d.pw = l["p"]
+            d.count_include_pad = 1 if l.get("count_include_pad", True) else 0
+            d.return_indices = 1 if l.get("return_indices", False) else 0
+            d.ceil_mode = 1 if l.get("ceil_mode", False) else 0
+            dil = l.get("dilation", (1, 1))
+            d.dilation_h, d.dilation_w = dil
+        else:
+            raise ValueError(f"unknown layer kind {kind!r}")
+    return arr, keep
+
+
+def bs_stack_create(layers, in_shape, dtype) -> int:
+    """Returns the opaque handle (an int).  `dtype` is BS_F32/BS_BF16 or "f32"/"bf16"."""
+    dt = {"f32": BS_F32, "bf16": BS_BF16}.get(dtype, dtype)
+    arr, keep = _marshal_layers(layers, int(in_shape[1]))
+    h = C.c_void_p()
+    _check(load().bs_stack_create(arr, len(layers), _shape4(in_shape), int(dt), C.byref(h)),
+           "bs_stack_create")
+    del keep
+    return h.value
+
+
+def bs_stack_destroy(handle) -> None:
+    load().bs_stack_destroy(C.c_void_p(handle))
+
+
+def bs_stack_output_shape(handle):
+    out = (C.c_int64 * 4)()
+    _check(load().bs_stack_output_shape(C.c_void_p(handle), out), "bs_stack_output_shape")
+    return tuple(out)
+
+
+def bs_stack_num_residuals(handle) -> int:
+    return int(load().bs_stack_num_residuals(C.c_void_p(handle)))
+
+
+def bs_stack_residual_shape(handle, i):
+    out = (C.c_int64 * 4)()
+    _check(load().bs_stack_residual_shape(C.c_void_p(handle), int(i), out), "bs_stack_residual_shape")
+    return tuple(out)
+
+
+def bs_stack_num_index_outputs(handle) -> int:
+    return int(load().bs_stack_num_index_outputs(C.c_void_p(handle)))
+
+
+def bs_stack_index_shape(handle, i):
+    out = (C.c_int64 * 4)()
+    _check(load().bs_stack_index_shape(C.c_void_p(handle), int(i), out), "bs_stack_index_shape")
+    return tuple(out)
+
+
+def bs_stack_folded_bn(handle, layer, channels):
+    scale = np.empty(channels, np.float32)
+    shift = np.empty(channels, np.float32)
+    _check(load().bs_stack_folded_bn(C.c_void_p(handle), int(layer), scale.ctypes.data_as(_f32p),
+                                     shift.ctypes.data_as(_f32p)), "bs_stack_folded_bn")
+    return scale, shift
+
+
+def bs_stack_plan(handle, **opts) -> None:
+    o = bs_plan_options()
+    for k, v in opts.items():
+        if not hasattr(o, k) or k == "reserved":
+            raise TypeError(f"unknown plan option {k!r}")
+        setattr(o, k, int(v))
+    _check(load().bs_stack_plan(C.c_void_p(handle), C.byref(o) if opts else None), "bs_stack_plan")
+
+
+def _struct_dict(s):
+    out = {}
+    for name, _ in s._fields_:
+        v = getattr(s, name)
+        out[name] = tuple(v) if hasattr(v, "__len__") else v
+    return out
+
+
+def bs_stack_plan_info(handle) -> dict:
+    info = bs_plan_info()
+    _check(load().bs_stack_plan_info(C.c_void_p(handle), C.byref(info)), "bs_stack_plan_info")
+    return _struct_dict(info)
+
+
+def bs_stack_step_info(handle, step) -> dict:
+    info = bs_step_info()
+    _check(load().bs_stack_step_info(C.c_void_p(handle), int(step), C.byref(info)), "bs_stack_step_info")
+    return _struct_dict(info)
+
+
+def bs_stack_sequence_info(handle, seq) -> dict:
+    info = bs_sequence_info()
+    _check(load().bs_stack_sequence_info(C.c_void_p(handle), int(seq), C.byref(info)),
+           "bs_stack_sequence_info")
+    d = _struct_dict(info)
+    d["variant_name"] = VARIANT_NAMES.get(d["variant"], "?")
+    return d
+
+
+def bs_stack_operation_name(handle, op):
+    r = load().bs_stack_operation_name(C.c_void_p(handle), int(op))
+    return r.decode() if r else None
+
+
+def bs_stack_workspace_bytes(handle) -> int:
+    return int(load().bs_stack_workspace_bytes(C.c_void_p(handle)))
+
+
+def bs_stack_run(handle, in_ptr, residual_ptrs, out_ptr, index_ptrs, workspace_ptr, workspace_bytes,
+                 stream) -> None:
+    """All *_ptr arguments are integer device addresses (0 / None = NULL)."""
+    res = None
+    if residual_ptrs:
+        res = (C.c_void_p * len(residual_ptrs))(*[C.c_void_p(p or None) for p in residual_ptrs])
+    idx = None
+    if index_ptrs:
+        idx = (C.c_void_p * len(index_ptrs))(*[C.c_void_p(p or None) for p in index_ptrs])
+    _check(load().bs_stack_run(C.c_void_p(handle), C.c_void_p(in_ptr or None), res,
+                               C.c_void_p(out_ptr or None), idx, C.c_void_p(workspace_ptr or None),
+                               int(workspace_bytes), C.c_void_p(stream or None)), "bs_stack_run")
+
+
+# ---- convenience wrapper -----------------------------------------------------------------
+class Stack:
+    """A planned stack bound to torch tensors (device memory and streams only)."""
+
+    def __init__(self, layers, in_shape, dtype="f32"):
+        self.dtype = dtype
+        self.in_shape = tuple(int(v) for v in in_shape)
+        self.handle = bs_stack_create(layers, self.in_shape, dtype)
+        self.out_shape = bs_stack_output_shape(self.handle)
+        self.n_res = bs_stack_num_residuals(self.handle)
+        self.n_idx = bs_stack_num_index_outputs(self.handle)
+        self._workspace = None
+
+    def close(self):
+        if getattr(self, "handle", None):
+            bs_stack_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+    def plan(self, **opts):
+        bs_stack_plan(self.handle, **opts)
+        self._workspace = None
+        return self
+
+    def info(self) -> dict:
+        p = bs_stack_plan_info(self.handle)
+        p["operations"] = [bs_stack_operation_name(self.handle, i) for i in range(p["n_operations"])]
+        p["steps"] = [bs_stack_step_info(self.handle, i) for i in range(p["n_steps"])]
+        p["sequences"] = [bs_stack_sequence_info(self.handle, i) for i in range(p["n_sequences"])]
+        return p
+
+    def torch_dtype(self):
+        import torch
+        return torch.float32 if self.dtype in ("f32", BS_F32) else torch.bfloat16
+
+    def alloc_outputs(self, device="cuda", indices=True):
+        import torch
+        out = torch.empty(self.out_shape, dtype=self.torch_dtype(), device=device)
+        idx = [torch.empty(bs_stack_index_shape(self.handle, i), dtype=torch.int32, device=device)
+               for i in range(self.n_idx)] if indices else []
+        return out, idx
+
+    def workspace(self, device="cuda"):
+        import torch
+        n = bs_stack_workspace_bytes(self.handle)
+        if n and (self._workspace is None or self._workspace.numel() < n):
+            self._workspace = torch.empty(n, dtype=torch.uint8, device=device)
+        return self._workspace if n else None
+
+    def run(self, x, residuals=(), out=None, indices=None, stream=None):
+        """Enqueue on `stream` (default: torch's current stream); returns (out, indices)."""
+        import torch
+        if tuple(x.shape) != self.in_shape or x.dtype != self.torch_dtype() or not x.is_contiguous():
+            raise ValueError("input must be a contiguous tensor of the stack's shape and dtype")
+        for r in residuals:
+            if r.dtype != self.torch_dtype() or not r.is_contiguous():
+                raise ValueError("residuals must be contiguous tensors of the stack's dtype")
+        if out is None or indices is None:
+            o2, i2 = self.alloc_outputs(x.device, indices is None)
+            out = o2 if out is None else out
+            indices = i2 if indices is None else indices
+        ws = self.workspace(x.device)
+        st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        bs_stack_run(self.handle, x.data_ptr(), [r.data_ptr() for r in residuals], out.data_ptr(),
+                     [t.data_ptr() if t is not None else 0 for t in indices] if indices else None,
+                     ws.data_ptr() if ws is not None else 0, ws.numel() if ws is not None else 0, st)
+        return out, indices

@@ -1,0 +1,47 @@
+"""Build libbrainslug_hip.so (hipcc, gfx950) in-tree, next to this file."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libbrainslug_hip.so")
+SOURCES = ["bs_stack.cpp", "bs_plan.cpp", "bs_run.cpp", "bs_kernels.hip"]
+
+# -ffp-contract=off: the only fused multiply-add is the explicit one of BatchNorm.
+# packed-fp32 instructions are disabled for the device code.
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
+         "-fno-fast-math", "-fvisibility=hidden", "-Wall", "-Wextra", "-Wno-unused-parameter",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def sources():
+    return [os.path.join(CSRC, s) for s in SOURCES]
+
+
+def up_to_date() -> bool:
+    if not os.path.exists(LIB):
+        return False
+    t = os.path.getmtime(LIB)
+    deps = sources() + [os.path.join(CSRC, "bs_internal.h"), os.path.join(ROOT, "include", "brainslug.h")]
+    return all(os.path.getmtime(d) <= t for d in deps)
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    if not force and up_to_date():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    cmd = [hipcc, *FLAGS, "-x", "hip", *sources(), "-o", tmp]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

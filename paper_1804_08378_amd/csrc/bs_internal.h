@@ -1,0 +1,245 @@
+// Internal declarations shared by the host side (stack, planner, run) and the HIP
+// kernels of libbrainslug_hip.  Nothing here is part of the public C ABI.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "brainslug.h"
+
+namespace bs {
+
+// ---------------------------------------------------------------------------
+// Basic operations a layer maps to (Section 4.1 "collapse process": layers are
+// mapped onto element-wise and non-element-wise operations; Listing 2 shows
+// average pooling as AvgPooling + AvgNormalization).
+// ---------------------------------------------------------------------------
+enum OpKind : int32_t {
+    OP_BN = 1,
+    OP_RELU = 2,
+    OP_ADD = 3,
+    OP_MAXPOOL = 4,
+    OP_AVGSUM = 5,   // non-element-wise: window sum
+    OP_AVGNORM = 6,  // element-wise: multiply by 1/divisor
+};
+
+inline bool op_is_elementwise(int32_t k) { return k != OP_MAXPOOL && k != OP_AVGSUM; }
+
+struct Op {
+    int32_t kind = 0;
+    int32_t layer = -1;       // index in the layer list
+    int32_t kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0;
+    int32_t count_include_pad = 1;
+    int32_t idx_slot = -1;    // stack-wide index-output number (max pool with return_indices)
+    int32_t res_slot = -1;    // stack-wide residual number (Add)
+    int32_t param_off = -1;   // BN: float offset of scale[C] in the parameter table; shift follows
+    int32_t in_h = 0, in_w = 0, out_h = 0, out_w = 0;  // plane size before / after this op
+};
+
+struct Step {
+    int32_t first_op = 0, n_ops = 0, pool_op = -1, sequence = -1;
+};
+
+// ---------------------------------------------------------------------------
+// Kernel argument blocks (plain data, passed by value at launch).
+// ---------------------------------------------------------------------------
+constexpr int K_MAX_LEVELS = 8;   // pooling operations in one LDS sequence
+constexpr int K_MAX_EW = 6;       // element-wise operations attached to one level
+constexpr int K_MAX_STREAM_EW = 16;
+constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
+constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
+
+// n / d for 0 <= n < 2^31 by multiply-high and shift.
+struct FastDiv {
+    uint32_t mul = 0, shift = 0, d = 1;
+};
+FastDiv make_fastdiv(uint32_t d);
+
+struct EwOp {
+    int32_t kind;  // OP_BN, OP_RELU, OP_ADD
+    int32_t arg;   // BN: offset of scale[] in the parameter table; Add: residual slot of the sequence
+};
+
+struct PoolK {
+    int32_t kind;  // OP_MAXPOOL or OP_AVGSUM (normalisation included)
+    int32_t kh, kw, sh, sw, ph, pw;
+    int32_t count_include_pad;
+    int32_t idx_slot;  // slot in LdsSeqK::idx, or -1
+    float inv_kk;      // 1.0f / (kh * kw)
+};
+
+struct LevelK {
+    int32_t H, W;            // plane size at this level
+    int32_t rows_max, pitch; // largest tile region (rows) and LDS row pitch (elements)
+    int32_t plane_stride;    // rows_max * pitch
+    int32_t buf_off;         // float offset of this level's buffer in dynamic LDS
+    int32_t n_ew;
+    EwOp ew[K_MAX_EW];       // applied to a value once it exists at this level
+    FastDiv div_pitch;       // by pitch (level 0: by pitch / VEC)
+    FastDiv div_plane;       // by rows_max * pitch (level 0: rows_max * pitch / VEC)
+};
+
+struct LdsSeqK {
+    const void *in;
+    void *out;
+    const float *params;
+    const void *res[K_MAX_RES];
+    int32_t *idx[K_MAX_IDX];
+    int32_t n_levels;  // L >= 1 pooling operations; levels 0..L
+    int32_t NC, C;
+    int32_t TH, TW, tiles_h, tiles_w, PPG;
+    int32_t vec;       // elements per 128-bit access used for the level-0 load (1 = scalar)
+    FastDiv div_tiles_w, div_tiles_hw, div_c;
+    LevelK level[K_MAX_LEVELS + 1];
+    PoolK pool[K_MAX_LEVELS + 1];  // pool[l] produces level l from level l-1 (l >= 1)
+};
+
+struct StreamK {
+    const void *in;
+    void *out;
+    const float *params;
+    const void *res[K_MAX_RES];
+    int32_t n_ew;
+    EwOp ew[K_MAX_STREAM_EW];
+    uint32_t total;     // vectors (or elements when vec == 1)
+    int32_t C;
+    FastDiv div_plane;  // by H*W/vec
+    FastDiv div_c;
+};
+
+struct PoolDirectK {
+    const void *in;
+    void *out;
+    const float *params;
+    const void *res[K_MAX_RES];
+    int32_t *idx;
+    int32_t n_pre, n_post;
+    EwOp pre[K_MAX_EW], post[K_MAX_EW];
+    PoolK pool;
+    int32_t C, H, W, Ho, Wo;
+    uint32_t total;      // units = planes * Ho * (W / vec)
+    FastDiv div_wv;      // by W / vec
+    FastDiv div_ho;      // by Ho
+    FastDiv div_c;
+};
+
+// Region of level `level` that tile (ti, tj) of the final level depends on: walk the
+// windows of the pooling operations backwards and clip to the plane (cells outside the
+// plane are padding: never loaded, never computed).  Used by the kernel and, with the same
+// code, by the planner's bounds audit.
+struct Region {
+    int32_t r_lo, r_hi, c_lo, c_hi;
+};
+
+#if defined(__HIPCC__)
+#define BS_HD __host__ __device__ inline
+#else
+#define BS_HD inline
+#endif
+
+BS_HD Region region_at(const LdsSeqK &k, int32_t ti, int32_t tj, int32_t level)
+{
+    const int32_t L = k.n_levels;
+    Region g;
+    g.r_lo = ti * k.TH;
+    g.r_hi = g.r_lo + k.TH < k.level[L].H ? g.r_lo + k.TH : k.level[L].H;
+    g.c_lo = tj * k.TW;
+    g.c_hi = g.c_lo + k.TW < k.level[L].W ? g.c_lo + k.TW : k.level[L].W;
+    for (int32_t l = L; l > level; --l) {
+        const PoolK &p = k.pool[l];
+        const int32_t Hp = k.level[l - 1].H, Wp = k.level[l - 1].W;
+        const int32_t rl = g.r_lo * p.sh - p.ph, rh = (g.r_hi - 1) * p.sh - p.ph + p.kh;
+        const int32_t cl = g.c_lo * p.sw - p.pw, ch = (g.c_hi - 1) * p.sw - p.pw + p.kw;
+        g.r_lo = rl > 0 ? rl : 0;
+        g.r_hi = rh < Hp ? rh : Hp;
+        g.c_lo = cl > 0 ? cl : 0;
+        g.c_hi = ch < Wp ? ch : Wp;
+    }
+    if (level == 0 && k.vec > 1) {
+        g.c_lo = g.c_lo / k.vec * k.vec;
+        g.c_hi = (g.c_hi + k.vec - 1) / k.vec * k.vec;
+    }
+    return g;
+}
+
+enum KernelId : int32_t { KERNEL_STREAM = 1, KERNEL_POOL_DIRECT = 2, KERNEL_LDS = 3 };
+
+struct Sequence {
+    int32_t first_step = 0, n_steps = 0;
+    int32_t first_op = 0, n_ops = 0;
+    int32_t first_layer = 0, n_layers = 0;
+    int32_t variant = 0;
+    int32_t n_levels = 0;
+    int32_t tile_rows = 0, tile_cols = 0, planes_per_group = 1;
+    int32_t halo_rows = 0, halo_cols = 0;
+    int32_t threads = 256;
+    int32_t vec = 1;
+    int64_t grid = 0;
+    uint64_t lds_bytes = 0;
+    int64_t in_shape[4] = {0, 0, 0, 0}, out_shape[4] = {0, 0, 0, 0};
+    double redundancy = 1.0;
+    // which stack-wide residual / index slots the sequence-local slots refer to
+    int32_t n_res = 0, res_map[K_MAX_RES] = {-1, -1, -1, -1};
+    int32_t n_idx = 0, idx_map[K_MAX_IDX] = {-1, -1, -1, -1};
+    // argument blocks; pointers are filled in at run time
+    StreamK stream{};
+    PoolDirectK direct{};
+    LdsSeqK lds{};
+};
+
+struct Layer {
+    bs_layer_desc desc{};
+    std::vector<float> gamma, beta, mean, var;
+    std::vector<float> scale, shift;  // folded
+    int64_t in_shape[4] = {0, 0, 0, 0}, out_shape[4] = {0, 0, 0, 0};
+};
+
+struct Limits {
+    uint64_t max_lds_bytes = 0;
+    int32_t num_cus = 0;
+};
+
+}  // namespace bs
+
+struct bs_stack {
+    std::vector<bs::Layer> layers;
+    int64_t in_shape[4] = {0, 0, 0, 0}, out_shape[4] = {0, 0, 0, 0};
+    int32_t dtype = BS_F32;
+    int32_t n_res = 0, n_idx = 0;
+    int64_t res_shape[BS_MAX_RESIDUALS][4] = {};
+    int64_t idx_shape[BS_MAX_INDEX_OUTPUTS][4] = {};
+    bool has_pool = false;
+
+    // plan
+    bool planned = false, device_planned = false;
+    int device = -1;
+    bs_plan_options opts{};
+    std::vector<bs::Op> ops;
+    std::vector<bs::Step> steps;
+    std::vector<bs::Sequence> seqs;
+    std::vector<float> host_params;  // [scale(C), shift(C)] per BatchNorm, in op order
+    float *dev_params = nullptr;
+    uint64_t workspace_bytes = 0;
+    uint64_t ws_half_bytes = 0;  // size of each of the two ping-pong halves
+    uint64_t algorithmic_bytes = 0;
+};
+
+namespace bs {
+
+size_t dtype_size(int32_t dtype);
+
+// planner (host only)
+bs_status build_operations(bs_stack *s);
+bs_status group_steps(bs_stack *s);
+bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &lim);
+
+// device side (bs_kernels.hip)
+bs_status device_limits(Limits *lim, int *device);
+bs_status upload_params(bs_stack *s);
+void free_params(bs_stack *s);
+bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
+                          const void *const *res, int32_t *const *idx, void *stream);
+void set_hip_error(int32_t e);
+
+}  // namespace bs

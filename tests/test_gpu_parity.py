@@ -1,0 +1,234 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.
+
+Bars (the benchmark spec): max-pool argmax indices bit-exact; float32 values within
+1e-5 * max|ref|; bfloat16 within 1e-2 * max|ref|.  Both sides use the same fixed
+float32 operation order per layer, so values are in fact expected to be
+bit-identical; the count of differing elements is printed as a diagnostic.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import breadth_first as bf
+from paper_1804_08378_amd import brainslug as bs
+from paper_1804_08378_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+
+
+def _dev(a, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)  # inputs are bf16-representable: lossless
+    return t.cuda()
+
+
+def run_gpu(layers, x, res, dtype, **opts):
+    st = bs.Stack(layers, x.shape, dtype).plan(**opts)
+    out, idx = st.run(_dev(x, dtype), [_dev(r, dtype) for r in res])
+    torch.cuda.synchronize()
+    info = st.info()
+    o = out.float().cpu().numpy()
+    ii = [t.cpu().numpy() for t in idx]
+    st.close()
+    return o, ii, info
+
+
+def check(layers, x, res, dtype, label, **opts):
+    print(f"[parity] {label} shape={x.shape} dtype={dtype} opts={opts}", flush=True)
+    ref, ref_idx, _ = bf.run_stack(layers, x, res, dtype)
+    out, idx, info = run_gpu(layers, x, res, dtype, **opts)
+    assert out.shape == ref.shape
+    scale = float(np.abs(ref).max()) or 1.0
+    err = float(np.abs(out - ref).max())
+    ndiff = int((out.view(np.uint32) != ref.view(np.uint32)).sum())
+    print(f"         max|err|={err:.3e} (bar {TOL[dtype] * scale:.3e}) non-identical={ndiff} "
+          f"variants={[q['variant_name'] for q in info['sequences']]}", flush=True)
+    assert err <= TOL[dtype] * scale, label
+    assert len(idx) == len(ref_idx)
+    for k, (a, b) in enumerate(zip(idx, ref_idx)):
+        assert a.shape == b.shape
+        assert np.array_equal(a, b), f"{label}: argmax output {k} differs in {(a != b).sum()} cells"
+    assert ndiff == 0, f"{label}: values within tolerance but not bit-identical ({ndiff})"
+    return info
+
+
+def _shrunk(name, dtype, batch=2, indices=True, seed=0):
+    layers, x, res = wl.inputs_for(name, seed, dtype, batch=batch, indices=indices)
+    return layers, x, res
+
+
+# ------------------------------------------------------------------ named configs
+CASES = [(n, d) for n in wl.CONFIG_NAMES for d in wl.build(n)[2]]
+
+
+@pytest.mark.parametrize("name,dtype", CASES)
+def test_config_reduced_batch(name, dtype):
+    layers, x, res = _shrunk(name, dtype, batch=3)
+    check(layers, x, res, dtype, f"{name}/auto")
+
+
+@pytest.mark.parametrize("name,dtype", CASES)
+def test_config_layer_by_layer_plan_is_identical(name, dtype):
+    """Breadth-first plan (one kernel per layer, Figure 2) on the GPU: second witness."""
+    layers, x, res = _shrunk(name, dtype, batch=2)
+    info = check(layers, x, res, dtype, f"{name}/breadth_first", breadth_first=1)
+    assert info["n_sequences"] == len(layers)
+
+
+@pytest.mark.parametrize("name,dtype", [c for c in CASES if "pool" in
+                                        " ".join(l["kind"] for l in wl.build(c[0])[0])])
+@pytest.mark.parametrize("tile", [(3, 5, 1), (1, 1, 2), (7, 1000, 3)])
+def test_config_forced_lds_tiles(name, dtype, tile):
+    """Every pooling config through the LDS kernel with small, ragged tiles: halo
+    recompute, padding at tile edges, several planes per work-group."""
+    layers, x, res = _shrunk(name, dtype, batch=1)
+    c = min(x.shape[1], 5)
+    for l in layers:
+        if l["kind"] == "bn":
+            for key in ("gamma", "beta", "mean", "var"):
+                l[key] = l[key][:c]
+    x = np.ascontiguousarray(x[:, :c, :40, :36])
+    res = [np.ascontiguousarray(r[:, :c, :40, :36]) for r in res]
+    info = check(layers, x, res, dtype, f"{name}/lds{tile}", force_variant=bs.BS_VARIANT_LDS_TILE,
+                 tile_rows=tile[0], tile_cols=tile[1], planes_per_group=tile[2])
+    assert all(q["variant_name"] == "lds_tile" for q in info["sequences"])
+
+
+# ------------------------------------------------------------------ ragged shapes
+def _stacks(c):
+    return {
+        "bn_relu_max2": [wl.bn_params(c, 1), wl.relu(), wl.maxpool(2, 2, 0, True)],
+        "bn_relu_max3s2p1": [wl.bn_params(c, 2), wl.relu(), wl.maxpool(3, 2, 1, True)],
+        "bn_add_relu": [wl.bn_params(c, 3), wl.add(), wl.relu()],
+        "bn_relu_avg2": [wl.bn_params(c, 4), wl.relu(), wl.avgpool(2, 2)],
+        "halo_stress": [wl.bn_params(c, 5), wl.relu(), wl.avgpool(3, 1, 1, True),
+                        wl.maxpool(3, 2, 1, True), wl.bn_params(c, 6), wl.relu()],
+        "max_bn_relu_x3": sum(([wl.maxpool(3, 1, 1, True), wl.bn_params(c, 7 + i), wl.relu()]
+                               for i in range(3)), []),
+        "avg_nopad_div": [wl.relu(), wl.avgpool(3, 2, 1, False), wl.add(), wl.maxpool(2, 1, 0, True)],
+        "rect_windows": [wl.bn_params(c, 9), wl.maxpool((3, 2), (2, 1), (1, 0), True),
+                         wl.avgpool((2, 3), (1, 2), (1, 1), True)],
+        "add_after_pool": [wl.maxpool(2, 2, 0, True), wl.add(), wl.bn_params(c, 10), wl.relu(), wl.add()],
+        "max4_direct": [wl.bn_params(c, 11), wl.maxpool(4, 4, 0, True), wl.relu()],
+        "avg_1x2_direct": [wl.avgpool((1, 2), (1, 2), 0), wl.bn_params(c, 12)],
+        "stride_gt_kernel": [wl.bn_params(c, 13), wl.maxpool(2, 3, 0, True), wl.relu()],
+        "mid_idx_then_gap": [wl.maxpool(3, 1, 1, True), wl.relu(), wl.maxpool(2, 3, 0, True)],
+    }
+
+
+SHAPES = [(2, 3, 13, 11), (1, 1, 1, 1), (1, 2, 9, 16), (3, 5, 32, 24), (1, 7, 57, 61), (2, 4, 64, 64)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_shapes_all_stacks(shape, dtype):
+    for name, layers in _stacks(shape[1]).items():
+        if wl.output_shape(layers, shape)[2] < 1 or wl.output_shape(layers, shape)[3] < 1:
+            continue
+        try:
+            ok = all(v >= 1 for v in wl.output_shape(layers, shape))
+            # intermediate pools must not produce empty planes either
+            cur = shape
+            for l in layers:
+                cur = wl.output_shape([l], cur)
+                ok = ok and cur[2] >= 1 and cur[3] >= 1
+        except Exception:
+            ok = False
+        if not ok:
+            continue
+        x = wl.activation(shape, 30, dtype)
+        res = [wl.activation(s, 31 + i, dtype) for i, s in enumerate(wl.residual_shapes(layers, shape))]
+        check(layers, x, res, dtype, f"{name}{shape}/auto")
+        check(layers, x, res, dtype, f"{name}{shape}/steps1", max_steps_per_sequence=1)
+        if any(l["kind"] in ("maxpool", "avgpool") for l in layers):
+            check(layers, x, res, dtype, f"{name}{shape}/lds-small", force_variant=bs.BS_VARIANT_LDS_TILE,
+                  tile_rows=2, tile_cols=3, planes_per_group=2, max_lds_bytes=4096)
+
+
+def test_deep_synthetic_blocks_split_into_sequences():
+    """Section 5.1's block <MaxPool 3/1/1, BatchNorm, ReLU> repeated: with a small on-chip
+    budget the halo growth forces several sequences; results stay identical."""
+    c, blocks = 4, 12
+    layers = sum(([wl.maxpool(3, 1, 1, i % 5 == 0), wl.bn_params(c, 40 + i), wl.relu()]
+                  for i in range(blocks)), [])
+    x = wl.activation((2, c, 33, 29), 50)
+    for opts in ({}, {"max_steps_per_sequence": 1}, {"max_steps_per_sequence": 5},
+                 {"max_lds_bytes": 8192}, {"max_lds_bytes": 2048, "threads_per_group": 64}):
+        info = check(layers, x, [], "f32", f"blocks{blocks}/{opts}", **opts)
+        if opts.get("max_steps_per_sequence") == 1:
+            assert info["n_sequences"] == blocks
+        if opts.get("max_lds_bytes") == 8192:
+            assert info["n_sequences"] > 1
+
+
+def test_in_place_elementwise_and_stream_argument():
+    layers, x, res = _shrunk("resnet_tail", "f32", batch=1)
+    ref, _, _ = bf.run_stack(layers, x, res)
+    st = bs.Stack(layers, x.shape, "f32").plan()
+    xd, rd = _dev(x, "f32"), [_dev(r, "f32") for r in res]
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        st.run(xd, rd, out=xd, indices=[])  # out == in
+    s.synchronize()
+    assert np.array_equal(xd.cpu().numpy(), ref)
+
+
+def test_run_argument_errors():
+    layers, x, res = _shrunk("resnet_tail", "f32", batch=1)
+    st = bs.Stack(layers, x.shape, "f32")
+    xd, rd = _dev(x, "f32"), _dev(res[0], "f32")
+    out = torch.empty_like(xd)
+    h = st.handle
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.bs_stack_run(h, xd.data_ptr(), [rd.data_ptr()], out.data_ptr(), None, 0, 0, 0)
+    assert e.value.status == 5  # not planned
+    st.plan()
+    for args, status in [
+        ((0, [rd.data_ptr()], out.data_ptr()), 1),
+        ((xd.data_ptr(), None, out.data_ptr()), 1),
+        ((xd.data_ptr(), [0], out.data_ptr()), 1),
+        ((xd.data_ptr() + 4, [rd.data_ptr()], out.data_ptr()), 7),
+        ((xd.data_ptr(), [rd.data_ptr()], rd.data_ptr()), 12),
+    ]:
+        with pytest.raises(bs.BrainSlugError) as e:
+            bs.bs_stack_run(h, args[0], args[1], args[2], None, 0, 0, 0)
+        assert e.value.status == status, args
+    # pooled stack may not run in place; multi-sequence stack needs its workspace
+    layers2, x2, _ = _shrunk("halo_stress", "f32", batch=1)
+    st2 = bs.Stack(layers2, x2.shape, "f32").plan(max_steps_per_sequence=1)
+    x2d = _dev(x2, "f32")
+    o2, _ = st2.alloc_outputs()
+    assert bs.bs_stack_workspace_bytes(st2.handle) > 0
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.bs_stack_run(st2.handle, x2d.data_ptr(), None, o2.data_ptr(), None, 0, 0, 0)
+    assert e.value.status == 8
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.bs_stack_run(st2.handle, x2d.data_ptr(), None, x2d.data_ptr(), None, 0, 0, 0)
+    assert e.value.status == 12
+    torch.cuda.synchronize()
+
+
+def test_indices_can_be_skipped():
+    layers, x, res = _shrunk("resnet_stem", "f32", batch=1, indices=True)
+    ref, _, _ = bf.run_stack(layers, x, res)
+    st = bs.Stack(layers, x.shape, "f32").plan()
+    out, _ = st.run(_dev(x, "f32"), [], indices=[])
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), ref)
+
+
+# ------------------------------------------------------------------ full BASELINE sizes
+@pytest.mark.parametrize("name,dtype", [c for c in CASES if c[0] != "tiny"])
+def test_config_full_size(name, dtype):
+    """Whole tensors at the BASELINE sizes, in the launch configuration the benchmark
+    times (automatic plan, indices off as in the bandwidth runs, then on)."""
+    layers, x, res = wl.inputs_for(name, 0, dtype, indices=False)
+    check(layers, x, res, dtype, f"{name}/full")
+    if any(l["kind"] == "maxpool" for l in layers):
+        layers, x, res = wl.inputs_for(name, 0, dtype, indices=True)
+        check(layers, x, res, dtype, f"{name}/full+indices")
