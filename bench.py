@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused (depth-first) stack path on one MI355X.
+
+Workload (BASELINE config 1): the three VGG-16-BN shaped post-convolution stacks
+BN -> ReLU -> MaxPool 2x2/2 on fp32 tensors 32x64x224x224, 32x128x112x112 and
+32x256x56x56 (seeded synthetic N(0,1) activations; no network, weights or images).
+One "step" runs all three stacks once.  Inputs are resident in HBM before timing;
+every launch reads a buffer set that has not been touched for >= 1 GB of traffic
+(rotation), so the 256 MB last-level cache cannot serve it.
+
+Prints ONE JSON line on stdout: whole-step effective GB/s (algorithmic bytes /
+wall time), the roofline entry of the dominant kernel (the 64x224x224 stack),
+the speed-up over the layer-by-layer HIP plan, and the CPU oracle timed on a
+bounded sample.  `--all` adds a per-configuration table (stderr) for every
+BASELINE config and dtype.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+PAPER_CONTEXT = ("paper (GTX 1080 Ti / Xeon E5-2690v4, fp32, whole networks vs PyTorch 0.3): up to "
+                 "35.7% GPU and 41.1% CPU speed-up; VGG16-BN optimizable layers +146.7% (GPU)")
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class StackBench:
+    """One stack with `sets` rotating buffer sets on the GPU."""
+
+    def __init__(self, name, dtype, indices=False, min_rotation_bytes=1 << 30, seed=0, **plan_opts):
+        import torch
+        from paper_1804_08378_amd import brainslug as bs
+        from paper_1804_08378_amd import workloads as wl
+
+        self.name, self.dtype = name, dtype
+        layers, x, res = wl.inputs_for(name, seed, dtype, indices=indices)
+        self.layers, self.shape = layers, x.shape
+        self.bytes = wl.algorithmic_bytes(layers, x.shape, dtype, indices)
+        self.lbl_bytes = wl.layer_by_layer_bytes(layers, x.shape, dtype)
+        self.images = x.shape[0]
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        self.fused = bs.Stack(layers, x.shape, dtype).plan(**plan_opts)
+        self.lbl = bs.Stack(layers, x.shape, dtype).plan(breadth_first=1)
+        self.sets = min(64, max(2, -(-min_rotation_bytes // self.bytes)))
+        x0 = torch.from_numpy(x).to(tdt).cuda()
+        r0 = [torch.from_numpy(r).to(tdt).cuda() for r in res]
+        self.x = [x0] + [x0.clone() for _ in range(self.sets - 1)]
+        self.res = [r0] + [[r.clone() for r in r0] for _ in range(self.sets - 1)]
+        self.out, self.idx = [], []
+        for _ in range(self.sets):
+            o, i = self.fused.alloc_outputs("cuda", indices)
+            self.out.append(o)
+            self.idx.append(i)
+        self.fused.workspace("cuda")
+        self.lbl.workspace("cuda")
+        self.cursor = 0
+        self.info = self.fused.info()
+
+    def launch(self, which="fused"):
+        s = self.cursor
+        self.cursor = (self.cursor + 1) % self.sets
+        st = self.fused if which == "fused" else self.lbl
+        st.run(self.x[s], self.res[s], out=self.out[s], indices=self.idx[s])
+
+
+def time_steps(stacks, which, steps, warmup):
+    """Returns (wall ms per step, {stack name: mean kernel-region ms from HIP events})."""
+    import torch
+
+    for _ in range(warmup):
+        for sb in stacks:
+            sb.launch(which)
+    torch.cuda.synchronize()
+    ev = {sb.name: [] for sb in stacks}
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for sb in stacks:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            sb.launch(which)
+            b.record()
+            ev[sb.name].append((a, b))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in ev.items()}
+    mins = {k: min(a.elapsed_time(b) for a, b in v) for k, v in ev.items()}
+    return (t1 - t0) * 1e3 / steps, per, mins
+
+
+def cpu_baseline(names, dtype, batch):
+    """Time the breadth-first CPU oracle, as it stands, on a bounded sample (batch cut)."""
+    from oracle import breadth_first as bf
+    from oracle import layers as OL
+    from paper_1804_08378_amd import workloads as wl
+
+    total_bytes, total_t = 0, 0.0
+    for n in names:
+        layers, x, res = wl.inputs_for(n, 0, dtype, batch=batch)
+        t0 = time.perf_counter()
+        bf.run_stack(layers, x, res, dtype)
+        total_t += time.perf_counter() - t0
+        total_bytes += wl.algorithmic_bytes(layers, x.shape, dtype)
+    return {"value": round(total_bytes / total_t / 1e9, 3), "unit": "GB/s", "cores": OL.max_threads(),
+            "kind": "oracle", "seconds": round(total_t, 3),
+            "sample": f"stacks {'+'.join(names)} at batch {batch} (full workload: batch 32), one pass, "
+                      "same algorithmic-bytes metric"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--all", action="store_true", help="also report every BASELINE config (stderr)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-batch", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (the path shards over the batch with no "
+            "exchange; multi-GPU figures are not produced). Use --gpus 1.")
+        sys.exit(2)
+
+    import torch
+    from paper_1804_08378_amd import brainslug as bs
+    from paper_1804_08378_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU")
+        sys.exit(2)
+    bs.load()
+    log(bs.bs_version(), "|", torch.cuda.get_device_name(0))
+
+    stacks = [StackBench(n, "f32") for n in wl.VGG_STACKS]
+    step_bytes = sum(sb.bytes for sb in stacks)
+    ms, per, mins = time_steps(stacks, "fused", args.steps, args.warmup)
+    ms_lbl, per_lbl, _ = time_steps(stacks, "lbl", max(10, args.steps // 4), max(2, args.warmup // 2))
+    value = step_bytes / (ms * 1e-3) / 1e9
+    dom = stacks[0]
+    dom_ms = per[dom.name]
+    achieved = dom.bytes / (dom_ms * 1e-3) / 1e9
+    out = {
+        "metric": "fused-stack effective HBM GB/s (algorithmic bytes / time), 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "BASELINE config 1: VGG-16-BN stacks BN->ReLU->MaxPool2x2/2, fp32, "
+                               "batch 32, 64x224x224 + 128x112x112 + 256x56x56, indices off",
+                   "rotation_sets": [sb.sets for sb in stacks]},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
+        "images_per_s": round(dom.images / (ms * 1e-3), 1),
+        "speedup_vs_layer_by_layer": round(ms_lbl / ms, 3),
+        "layer_by_layer": {"ms_per_step": round(ms_lbl, 4),
+                           "GBps_of_its_own_traffic": round(sum(sb.lbl_bytes for sb in stacks) /
+                                                            (ms_lbl * 1e-3) / 1e9, 1)},
+        "per_stack": {sb.name: {"ms_mean": round(per[sb.name], 4), "ms_min": round(mins[sb.name], 4),
+                                "GBps": round(sb.bytes / (per[sb.name] * 1e-3) / 1e9, 1),
+                                "variant": [q["variant_name"] for q in sb.info["sequences"]]}
+                      for sb in stacks},
+        "roofline": {"bound": "hbm", "kernel": "pool_direct_kernel<f32,4,2,2> on 32x64x224x224",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": dom.bytes, "avg_launch_ms": round(dom_ms, 4)},
+        "context": PAPER_CONTEXT,
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            with open(traffic_file) as f:
+                out["roofline"]["traffic"] = json.load(f).get("vgg_a_f32_bytes_per_launch")
+        except Exception:
+            pass
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl.VGG_STACKS, "f32", args.cpu_batch)
+    else:
+        out["cpu_baseline"] = None
+
+    if args.all:
+        del stacks
+        torch.cuda.empty_cache()
+        # context: a plain device-to-device copy (read N + write N bytes) of the largest input
+        src = [torch.empty(411041792 // 4, dtype=torch.float32, device="cuda").normal_() for _ in range(3)]
+        dst = [torch.empty_like(t) for t in src]
+        for i in range(6):
+            dst[i % 3].copy_(src[i % 3])
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(30):
+            dst[i % 3].copy_(src[i % 3])
+        b.record()
+        torch.cuda.synchronize()
+        out["copy_GBps_context"] = round(2 * 411041792 * 30 / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+        log("plain copy (torch copy_, 411 MB read + 411 MB write):", out["copy_GBps_context"], "GB/s")
+        del src, dst
+        torch.cuda.empty_cache()
+        log(f"{'config':<16}{'dtype':<6}{'variant':<13}{'MB':>8}{'us mean':>9}{'us min':>8}{'GB/s':>8}"
+            f"{'%peak':>7}{'img/s':>10}{'lbl us':>9}{'speedup':>8}")
+        rows = []
+        for name in wl.CONFIG_NAMES:
+            for dt in wl.build(name)[2]:
+                for idx in ([False, True] if any(l["kind"] == "maxpool" for l in wl.build(name)[0]) else [False]):
+                    sb = StackBench(name, dt, indices=idx)
+                    m, p, mn = time_steps([sb], "fused", args.steps, args.warmup)
+                    ml, pl, _ = time_steps([sb], "lbl", max(10, args.steps // 4), 2)
+                    g = sb.bytes / (p[name] * 1e-3) / 1e9
+                    row = {"config": name + ("+idx" if idx else ""), "dtype": dt,
+                           "variant": sb.info["sequences"][0]["variant_name"], "MB": sb.bytes / 1e6,
+                           "us_mean": p[name] * 1e3, "us_min": mn[name] * 1e3, "GBps": g,
+                           "pct_peak": 100 * g / HBM_PEAK_GBPS, "img_s": sb.images / (p[name] * 1e-3),
+                           "lbl_us": pl[name] * 1e3, "speedup": pl[name] / p[name]}
+                    rows.append(row)
+                    log(f"{row['config']:<16}{dt:<6}{row['variant']:<13}{row['MB']:>8.1f}{row['us_mean']:>9.1f}"
+                        f"{row['us_min']:>8.1f}{g:>8.0f}{row['pct_peak']:>7.1f}{row['img_s']:>10.0f}"
+                        f"{row['lbl_us']:>9.1f}{row['speedup']:>8.2f}")
+                    del sb
+                    torch.cuda.empty_cache()
+        out["all_configs"] = rows
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

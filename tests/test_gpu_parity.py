@@ -207,8 +207,10 @@ def test_run_argument_errors():
     with pytest.raises(bs.BrainSlugError) as e:
         bs.bs_stack_run(st2.handle, x2d.data_ptr(), None, o2.data_ptr(), None, 0, 0, 0)
     assert e.value.status == 8
+    ws = st2.workspace()
     with pytest.raises(bs.BrainSlugError) as e:
-        bs.bs_stack_run(st2.handle, x2d.data_ptr(), None, x2d.data_ptr(), None, 0, 0, 0)
+        bs.bs_stack_run(st2.handle, x2d.data_ptr(), None, x2d.data_ptr(), None, ws.data_ptr(),
+                        ws.numel(), 0)
     assert e.value.status == 12
     torch.cuda.synchronize()
 
