@@ -49,6 +49,8 @@ constexpr int K_MAX_EW = 6;       // element-wise operations attached to one lev
 constexpr int K_MAX_STREAM_EW = 16;
 constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
+constexpr int K_STREAM_U = 4;     // 128-bit vectors per lane in stream_kernel
+constexpr int K_DIRECT_U = 2;     // units per lane in pool_direct_kernel
 
 // n / d for 0 <= n < 2^31 by multiply-high and shift.
 struct FastDiv {
@@ -69,15 +71,20 @@ struct PoolK {
     float inv_kk;      // 1.0f / (kh * kw)
 };
 
+// One level of an LDS sequence.  The region a work-group keeps of level l is a fixed-size
+// rectangle rows x cols whose origin (which may lie outside the plane: padding) follows
+// from the tile by origin[l-1] = origin[l] * stride - pad.
 struct LevelK {
     int32_t H, W;            // plane size at this level
-    int32_t rows_max, pitch; // largest tile region (rows) and LDS row pitch (elements)
-    int32_t plane_stride;    // rows_max * pitch
+    int32_t rows, cols;      // region extent; cols is a multiple of 4 for levels >= 1
+    int32_t pitch;           // LDS row pitch in floats (multiple of 4)
+    int32_t plane_stride;    // rows * pitch
     int32_t buf_off;         // float offset of this level's buffer in dynamic LDS
     int32_t n_ew;
     EwOp ew[K_MAX_EW];       // applied to a value once it exists at this level
-    FastDiv div_pitch;       // by pitch (level 0: by pitch / VEC)
-    FastDiv div_plane;       // by rows_max * pitch (level 0: rows_max * pitch / VEC)
+    int32_t items_per_row;   // level 0: global vectors per region row; else strips of 4 outputs
+    FastDiv div_row;         // by items_per_row
+    FastDiv div_plane;       // by rows * items_per_row
 };
 
 struct LdsSeqK {
@@ -124,12 +131,10 @@ struct PoolDirectK {
     FastDiv div_c;
 };
 
-// Region of level `level` that tile (ti, tj) of the final level depends on: walk the
-// windows of the pooling operations backwards and clip to the plane (cells outside the
-// plane are padding: never loaded, never computed).  Used by the kernel and, with the same
-// code, by the planner's bounds audit.
-struct Region {
-    int32_t r_lo, r_hi, c_lo, c_hi;
+// Origin (global row / column of LDS cell 0,0) of every level's region for tile (ti, tj).
+// Used by the kernel and, with the same code, by the planner's bounds audit.
+struct Origins {
+    int32_t r[K_MAX_LEVELS + 1], c[K_MAX_LEVELS + 1];
 };
 
 #if defined(__HIPCC__)
@@ -138,29 +143,10 @@ struct Region {
 #define BS_HD inline
 #endif
 
-BS_HD Region region_at(const LdsSeqK &k, int32_t ti, int32_t tj, int32_t level)
+BS_HD void origin_step(const PoolK &p, int32_t &r0, int32_t &c0)
 {
-    const int32_t L = k.n_levels;
-    Region g;
-    g.r_lo = ti * k.TH;
-    g.r_hi = g.r_lo + k.TH < k.level[L].H ? g.r_lo + k.TH : k.level[L].H;
-    g.c_lo = tj * k.TW;
-    g.c_hi = g.c_lo + k.TW < k.level[L].W ? g.c_lo + k.TW : k.level[L].W;
-    for (int32_t l = L; l > level; --l) {
-        const PoolK &p = k.pool[l];
-        const int32_t Hp = k.level[l - 1].H, Wp = k.level[l - 1].W;
-        const int32_t rl = g.r_lo * p.sh - p.ph, rh = (g.r_hi - 1) * p.sh - p.ph + p.kh;
-        const int32_t cl = g.c_lo * p.sw - p.pw, ch = (g.c_hi - 1) * p.sw - p.pw + p.kw;
-        g.r_lo = rl > 0 ? rl : 0;
-        g.r_hi = rh < Hp ? rh : Hp;
-        g.c_lo = cl > 0 ? cl : 0;
-        g.c_hi = ch < Wp ? ch : Wp;
-    }
-    if (level == 0 && k.vec > 1) {
-        g.c_lo = g.c_lo / k.vec * k.vec;
-        g.c_hi = (g.c_hi + k.vec - 1) / k.vec * k.vec;
-    }
-    return g;
+    r0 = r0 * p.sh - p.ph;
+    c0 = c0 * p.sw - p.pw;
 }
 
 enum KernelId : int32_t { KERNEL_STREAM = 1, KERNEL_POOL_DIRECT = 2, KERNEL_LDS = 3 };

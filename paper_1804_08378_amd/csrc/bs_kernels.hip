@@ -143,25 +143,31 @@ BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
 }
 
 // ------------------------------------------------------ element-wise operations
-// Apply a list of element-wise operations to U register vectors at once (the list is
-// wave-uniform, so its interpretation costs scalar instructions only).
+// Apply a list of element-wise operations to U register vectors at once.  The list is
+// wave-uniform, so interpreting it costs scalar instructions only.  Lanes that have no
+// work carry c = 0 / off = 0 (safe addresses) and simply compute values nobody stores:
+// no load here is predicated.
 //   c[u]    channel of vector u (BatchNorm parameters)
 //   off[u]  element offset of vector u in this level's tensors (residual loads)
 template <bool BF16, int VEC, int U>
-BS_DEV void apply_ew(float (&x)[U][VEC], const bool (&valid)[U], const int32_t (&c)[U],
-                     const uint32_t (&off)[U], const EwOp *ew, int32_t n_ew, const float *params,
-                     int32_t C, const void *const *res)
+BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (&off)[U],
+                     const EwOp *ew, int32_t n_ew, const float *__restrict__ params, int32_t C,
+                     const void *const *res)
 {
+#pragma clang loop unroll(disable)
     for (int32_t j = 0; j < n_ew; ++j) {
         const int32_t kind = ew[j].kind, arg = ew[j].arg;
         if (kind == OP_BN) {
+            float sc[U], sh[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (!valid[u]) continue;
-                const float sc = params[arg + c[u]], sh = params[arg + C + c[u]];
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<BF16>(__builtin_fmaf(x[u][i], sc, sh));
+                sc[u] = params[arg + c[u]];
+                sh[u] = params[arg + C + c[u]];
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<BF16>(__builtin_fmaf(x[u][i], sc[u], sh[u]));
         } else if (kind == OP_RELU) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -171,11 +177,9 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const bool (&valid)[U], const int32_t (
             const void *rp = res[arg];
             Raw<BF16, VEC> rr[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (valid[u]) rr[u] = load_raw<BF16, VEC>(rp, off[u]);
+            for (int u = 0; u < U; ++u) rr[u] = load_raw<BF16, VEC>(rp, off[u]);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (!valid[u]) continue;
                 float r[VEC];
                 unpack<BF16, VEC>(rr[u], r);
 #pragma unroll
@@ -186,12 +190,12 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const bool (&valid)[U], const int32_t (
 }
 
 // =============================================================================
-// stream_kernel: element-wise only sequence.
+// stream_kernel: element-wise only sequence.  A work-group takes nthr * U
+// consecutive 128-bit vectors; lane t handles vectors t, t + nthr, ...
 // =============================================================================
-template <bool BF16, int VEC>
+template <bool BF16, int VEC, int U>
 __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
 {
-    constexpr int U = 4;
     const uint32_t nthr = blockDim.x;
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
     Raw<BF16, VEC> raw[U];
@@ -200,25 +204,18 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
     int32_t c[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * nthr;
+        uint32_t i = base + u * nthr;
         valid[u] = i < k.total;
+        i = valid[u] ? i : 0u;
         off[u] = i * VEC;
-        if (valid[u]) raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
+        raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
+        const uint32_t plane = fdiv(i, k.div_plane);
+        c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
     }
     float x[U][VEC];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * nthr;
-        const uint32_t plane = fdiv(i, k.div_plane);
-        c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
-        if (valid[u]) unpack<BF16, VEC>(raw[u], x[u]);
-        else {
-            c[u] = 0;
-#pragma unroll
-            for (int i2 = 0; i2 < VEC; ++i2) x[u][i2] = 0.0f;
-        }
-    }
-    apply_ew<BF16, VEC, U>(x, valid, c, off, k.ew, k.n_ew, k.params, k.C, k.res);
+    for (int u = 0; u < U; ++u) unpack<BF16, VEC>(raw[u], x[u]);
+    apply_ew<BF16, VEC, U>(x, c, off, k.ew, k.n_ew, k.params, k.C, k.res);
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (valid[u]) store_elems<BF16, VEC>(k.out, off[u], x[u]);
@@ -228,12 +225,12 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
 // pool_direct_kernel: [element-wise]* pool(k == s, p == 0) [element-wise]*,
 // windows disjoint, one 128-bit column block (VEC input columns) per unit.
 // unit = (plane, output row oh, column block cv); it reads KH rows x VEC columns and
-// produces VEC / KW outputs.
+// produces VEC / KW outputs.  Consecutive lanes take consecutive column blocks, so each
+// row load of a wave is one contiguous run.
 // =============================================================================
-template <bool BF16, int VEC, int KH, int KW>
+template <bool BF16, int VEC, int KH, int KW, int U>
 __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 {
-    constexpr int U = 2;
     constexpr int NO = VEC / KW;  // outputs per unit
     const uint32_t nthr = blockDim.x;
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
@@ -241,63 +238,77 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 
     Raw<BF16, VEC> raw[U][KH];
     bool valid[U];
-    uint32_t in_off[U], out_off[U], oh[U], cv[U], plane[U];
+    uint32_t in_off[U], out_off[U], idx0[U];
     int32_t c[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t i = base + u * nthr;
+        uint32_t i = base + u * nthr;
         valid[u] = i < k.total;
+        i = valid[u] ? i : 0u;
         const uint32_t t = fdiv(i, k.div_wv);
-        cv[u] = i - t * wv;
-        plane[u] = fdiv(t, k.div_ho);
-        oh[u] = t - plane[u] * (uint32_t)k.Ho;
-        c[u] = (int32_t)(plane[u] - fdiv(plane[u], k.div_c) * (uint32_t)k.C);
-        in_off[u] = (plane[u] * (uint32_t)k.H + oh[u] * KH) * (uint32_t)k.W + cv[u] * VEC;
-        out_off[u] = (plane[u] * (uint32_t)k.Ho + oh[u]) * (uint32_t)k.Wo + cv[u] * NO;
-        if (!valid[u]) c[u] = 0;
+        const uint32_t cv = i - t * wv;
+        const uint32_t plane = fdiv(t, k.div_ho);
+        const uint32_t oh = t - plane * (uint32_t)k.Ho;
+        c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+        idx0[u] = (oh * KH) * (uint32_t)k.W + cv * VEC;  // first cell of the unit in its plane
+        in_off[u] = plane * (uint32_t)(k.H * k.W) + idx0[u];
+        out_off[u] = (plane * (uint32_t)k.Ho + oh) * (uint32_t)k.Wo + cv * NO;
 #pragma unroll
-        for (int dh = 0; dh < KH; ++dh)
-            if (valid[u]) raw[u][dh] = load_raw<BF16, VEC>(k.in, in_off[u] + dh * (uint32_t)k.W);
+        for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<BF16, VEC>(k.in, in_off[u] + dh * (uint32_t)k.W);
     }
 
     float y[U][NO];
     int32_t yi[U][NO];
+    const bool is_max = k.pool.kind == OP_MAXPOOL;
+    const bool want_idx = k.idx != nullptr;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         float x[KH][VEC];
-        bool v1[KH];
         int32_t c1[KH];
         uint32_t o1[KH];
 #pragma unroll
         for (int dh = 0; dh < KH; ++dh) {
-            v1[dh] = valid[u];
             c1[dh] = c[u];
             o1[dh] = in_off[u] + dh * (uint32_t)k.W;
-            if (valid[u]) unpack<BF16, VEC>(raw[u][dh], x[dh]);
-            else {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) x[dh][i] = 0.0f;
-            }
+            unpack<BF16, VEC>(raw[u][dh], x[dh]);
         }
-        apply_ew<BF16, VEC, KH>(x, v1, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
-        const bool is_max = k.pool.kind == OP_MAXPOOL;
+        apply_ew<BF16, VEC, KH>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
+        if (is_max) {
+            if (want_idx) {
 #pragma unroll
-        for (int j = 0; j < NO; ++j) {
-            if (is_max) {
-                float best = -INFINITY;
-                int32_t bi = (int32_t)((oh[u] * KH) * (uint32_t)k.W + cv[u] * VEC + j * KW);
+                for (int j = 0; j < NO; ++j) {
+                    float best = -INFINITY;
+                    int32_t bi = (int32_t)idx0[u] + j * KW;
 #pragma unroll
-                for (int dh = 0; dh < KH; ++dh)
+                    for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
-                    for (int dw = 0; dw < KW; ++dw) {
-                        const float v = x[dh][j * KW + dw];
-                        const bool g = v > best;
-                        best = g ? v : best;
-                        bi = g ? (int32_t)((oh[u] * KH + dh) * (uint32_t)k.W + cv[u] * VEC + j * KW + dw) : bi;
-                    }
-                y[u][j] = best;
-                yi[u][j] = bi;
+                        for (int dw = 0; dw < KW; ++dw) {
+                            const float v = x[dh][j * KW + dw];
+                            const bool g = v > best;
+                            best = g ? v : best;
+                            bi = g ? (int32_t)(idx0[u] + dh * (uint32_t)k.W) + j * KW + dw : bi;
+                        }
+                    y[u][j] = best;
+                    yi[u][j] = bi;
+                }
             } else {
+#pragma unroll
+                for (int j = 0; j < NO; ++j) {
+                    float best = -INFINITY;
+#pragma unroll
+                    for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                        for (int dw = 0; dw < KW; ++dw) {
+                            const float v = x[dh][j * KW + dw];
+                            best = v > best ? v : best;
+                        }
+                    y[u][j] = best;
+                    yi[u][j] = 0;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NO; ++j) {
                 float sum = 0.0f;
 #pragma unroll
                 for (int dh = 0; dh < KH; ++dh)
@@ -308,12 +319,12 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
             }
         }
     }
-    apply_ew<BF16, NO, U>(y, valid, c, out_off, k.post, k.n_post, k.params, k.C, k.res);
+    apply_ew<BF16, NO, U>(y, c, out_off, k.post, k.n_post, k.params, k.C, k.res);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (!valid[u]) continue;
         store_elems<BF16, NO>(k.out, out_off[u], y[u]);
-        if (k.idx) {
+        if (want_idx && is_max) {
             int32_t *ip = k.idx + out_off[u];
             if constexpr (NO == 4) *reinterpret_cast<int4 *>(ip) = make_int4(yi[u][0], yi[u][1], yi[u][2], yi[u][3]);
             else if constexpr (NO == 2) *reinterpret_cast<int2 *>(ip) = make_int2(yi[u][0], yi[u][1]);
@@ -327,19 +338,128 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 
 // =============================================================================
 // lds_tile_kernel: depth-first execution of a multi-step (or overlapping-window)
-// sequence on one tile per work-group.
+// sequence, one tile per work-group.
 //
 // Levels: level 0 is the sequence input, pooling operation l (1..L) turns level l-1
-// into level l.  A work-group owns PPG planes x the tile [th*TH, +TH) x [tw*TW, +TW)
-// of level L.  The region of level l-1 it needs is found by walking the windows of
-// pooling operation l backwards and clipping to the plane: cells outside the plane are
-// that operation's padding (never a max candidate, nothing added to a sum) and are
-// neither loaded nor computed.  Level l (l < L) lives in LDS buffer l & 1.
+// into level l.  A work-group owns PPG planes x the TH x TW tile of level L whose
+// top-left output is (ti*TH, tj*TW).  For every level it keeps a fixed-size rectangle
+// (rows_l x cols_l) whose origin follows from the tile by origin[l-1] = origin[l] * s - p,
+// so the rectangle of level l-1 holds exactly the windows of the rectangle of level l.
+// Cells of a rectangle that fall outside the plane are the padding of the pooling
+// operation that will read them: they hold -inf for a max (never selected) and +0 for an
+// average (adding +0 to the running sum leaves it bit-identical, because a sum started at
+// +0 is never -0).  They are never computed from earlier layers.  Level l (l < L) lives in
+// LDS buffer l & 1; a barrier separates the phases (Section 4.4's two-buffer scheme).
+//
+// Phase 0 loads 128-bit global vectors and scatters them to LDS after the level-0
+// element-wise operations.  Phase l gives each lane a strip of four horizontally adjacent
+// outputs: it reads the kh rows x (3*sw + kw) columns it needs with 128/64/32-bit LDS reads
+// (strip starts are 16-byte aligned by construction) and keeps the windows in registers.
 // =============================================================================
+BS_DEV float pad_value(const PoolK &p) { return p.kind == OP_MAXPOOL ? -INFINITY : 0.0f; }
+
+// Read N consecutive floats starting at a 16-byte aligned LDS address.
+template <int N>
+BS_DEV void lds_read_row(const float *p, float (&r)[N])
+{
+    constexpr int Q = N / 4, R = N % 4;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const float4 t = *reinterpret_cast<const float4 *>(p + 4 * q);
+        r[4 * q] = t.x; r[4 * q + 1] = t.y; r[4 * q + 2] = t.z; r[4 * q + 3] = t.w;
+    }
+    if constexpr (R >= 2) {
+        const float2 t = *reinterpret_cast<const float2 *>(p + 4 * Q);
+        r[4 * Q] = t.x; r[4 * Q + 1] = t.y;
+    }
+    if constexpr (R == 1) r[4 * Q] = p[4 * Q];
+    if constexpr (R == 3) r[4 * Q + 2] = p[4 * Q + 2];
+}
+
+// One strip of four outputs of pooling operation p from the cached level below.
+//   src      first cell of the strip's first window (row r*sh, column 4*j*sw of the region)
+//   h0, w0   global row / column of that cell in the input plane (may be negative: padding)
+// KW/SW > 0: compile-time window width / stride; 0: run-time (scalar reads).
+template <int KW, int SW, bool WANT_IDX>
+BS_DEV void pool_strip(const PoolK &p, const float *src, int32_t pitch, int32_t h0, int32_t w0,
+                       int32_t Hp, int32_t Wp, float (&val)[4], int32_t (&bidx)[4])
+{
+    const bool is_max = p.kind == OP_MAXPOOL;
+    const int32_t kw = KW > 0 ? KW : p.kw, sw = SW > 0 ? SW : p.sw;
+    if (is_max) {
+        float best[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            best[e] = -INFINITY;
+            if constexpr (WANT_IDX) bidx[e] = max(h0, 0) * Wp + max(w0 + e * sw, 0);  // first in-range cell
+        }
+        for (int32_t dh = 0; dh < p.kh; ++dh) {
+            const float *rowp = src + dh * pitch;
+            const int32_t rbase = (h0 + dh) * Wp + w0;
+            if constexpr (KW > 0) {
+                constexpr int NCOL = 3 * SW + KW;
+                float r[NCOL];
+                lds_read_row<NCOL>(rowp, r);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw) {
+                        const float v = r[e * SW + dw];
+                        const bool g = v > best[e];
+                        best[e] = g ? v : best[e];
+                        if constexpr (WANT_IDX) bidx[e] = g ? rbase + e * SW + dw : bidx[e];
+                    }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    for (int32_t dw = 0; dw < kw; ++dw) {
+                        const float v = rowp[e * sw + dw];
+                        const bool g = v > best[e];
+                        best[e] = g ? v : best[e];
+                        if constexpr (WANT_IDX) bidx[e] = g ? rbase + e * sw + dw : bidx[e];
+                    }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) val[e] = best[e];
+    } else {
+        float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int32_t dh = 0; dh < p.kh; ++dh) {
+            const float *rowp = src + dh * pitch;
+            if constexpr (KW > 0) {
+                constexpr int NCOL = 3 * SW + KW;
+                float r[NCOL];
+                lds_read_row<NCOL>(rowp, r);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw) sum[e] = sum[e] + r[e * SW + dw];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    for (int32_t dw = 0; dw < kw; ++dw) sum[e] = sum[e] + rowp[e * sw + dw];
+            }
+        }
+        if (p.count_include_pad) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) val[e] = sum[e] * p.inv_kk;
+        } else {
+            const int32_t nr = min(h0 + p.kh, Hp) - max(h0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t we = w0 + e * sw;
+                const int32_t nc = min(we + kw, Wp) - max(we, 0);
+                // cells outside the plane can make nr * nc <= 0; those outputs are never stored
+                val[e] = sum[e] * (1.0f / (float)max(nr * nc, 1));
+            }
+        }
+    }
+}
+
 template <bool BF16, int VEC>
 __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
 {
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];
     const uint32_t tid = threadIdx.x, nthr = blockDim.x;
     const int32_t L = k.n_levels;
 
@@ -354,52 +474,51 @@ __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
     // ---------------- phase 0: load the level-0 region, apply its element-wise ops ----
     {
         const LevelK &lv = k.level[0];
-        const Region g = region_at(k, ti, tj, 0);
-        const int32_t rh = g.r_hi - g.r_lo, rwv = (g.c_hi - g.c_lo) / VEC;
-        const uint32_t pitchv = (uint32_t)lv.pitch / VEC;
-        const uint32_t planev = (uint32_t)lv.plane_stride / VEC;
-        const uint32_t items = (uint32_t)k.PPG * planev;
+        int32_t r0 = ti * k.TH, c0 = tj * k.TW;
+        for (int32_t l = L; l >= 1; --l) origin_step(k.pool[l], r0, c0);
+        const float padv = pad_value(k.pool[1]);
+        // first global vector column touching the region (floor division of a possibly
+        // negative column)
+        const int32_t gv0 = (c0 + 4096 * VEC) / VEC - 4096;
+        const uint32_t nvr = (uint32_t)lv.items_per_row;
+        const uint32_t per_plane = (uint32_t)lv.rows * nvr;
+        const uint32_t items = (uint32_t)nplanes * per_plane;
         float *dst = lds + lv.buf_off;
-        constexpr int U = 4;
+        constexpr int U = (VEC == 8) ? 2 : 4;
         for (uint32_t base = tid; base < items; base += nthr * U) {
             Raw<BF16, VEC> raw[U];
-            bool valid[U];
-            uint32_t off[U], loff[U];
-            int32_t c[U];
+            bool live[U], inimg[U];
+            uint32_t off[U];
+            int32_t c[U], lrow[U], lcol[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const uint32_t i = base + u * nthr;
+                uint32_t i = base + u * nthr;
+                live[u] = i < items;
+                i = live[u] ? i : 0u;
                 const uint32_t pl = fdiv(i, lv.div_plane);
-                const uint32_t rem = i - pl * planev;
-                const uint32_t r = fdiv(rem, lv.div_pitch);
-                const uint32_t cvv = rem - r * pitchv;
-                valid[u] = i < items && (int32_t)pl < nplanes && (int32_t)r < rh && (int32_t)cvv < rwv;
+                const uint32_t rem = i - pl * per_plane;
+                const uint32_t r = fdiv(rem, lv.div_row);
+                const uint32_t v = rem - r * nvr;
+                const int32_t gr = r0 + (int32_t)r, gc = (gv0 + (int32_t)v) * VEC;
+                inimg[u] = gr >= 0 && gr < lv.H && gc >= 0 && gc < lv.W;
                 const uint32_t plane = (uint32_t)plane0 + pl;
-                c[u] = valid[u] ? (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C) : 0;
-                off[u] = (plane * (uint32_t)lv.H + (uint32_t)g.r_lo + r) * (uint32_t)lv.W + (uint32_t)g.c_lo + cvv * VEC;
-                loff[u] = pl * (uint32_t)lv.plane_stride + r * (uint32_t)lv.pitch + cvv * VEC;
-                if (valid[u]) raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
+                c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+                off[u] = inimg[u] ? (plane * (uint32_t)lv.H + (uint32_t)gr) * (uint32_t)lv.W + (uint32_t)gc : 0u;
+                lrow[u] = (int32_t)(pl * (uint32_t)lv.plane_stride + r * (uint32_t)lv.pitch);
+                lcol[u] = gc - c0;
+                raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
             }
             float x[U][VEC];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (valid[u]) unpack<BF16, VEC>(raw[u], x[u]);
-                else {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) x[u][i] = 0.0f;
-                }
-            }
-            apply_ew<BF16, VEC, U>(x, valid, c, off, lv.ew, lv.n_ew, k.params, k.C, k.res);
+            for (int u = 0; u < U; ++u) unpack<BF16, VEC>(raw[u], x[u]);
+            apply_ew<BF16, VEC, U>(x, c, off, lv.ew, lv.n_ew, k.params, k.C, k.res);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (!valid[u]) continue;
-                if constexpr (VEC >= 4) {
+                if (!live[u]) continue;
 #pragma unroll
-                    for (int h = 0; h < VEC / 4; ++h)
-                        *reinterpret_cast<float4 *>(dst + loff[u] + 4 * h) =
-                            make_float4(x[u][4 * h], x[u][4 * h + 1], x[u][4 * h + 2], x[u][4 * h + 3]);
-                } else {
-                    dst[loff[u]] = x[u][0];
+                for (int e = 0; e < VEC; ++e) {
+                    const int32_t lc = lcol[u] + e;
+                    if (lc >= 0 && lc < lv.cols) dst[lrow[u] + lc] = inimg[u] ? x[u][e] : padv;
                 }
             }
         }
@@ -411,69 +530,100 @@ __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
         const LevelK &lv = k.level[l];
         const LevelK &pv = k.level[l - 1];
         const PoolK &p = k.pool[l];
-        const Region g = region_at(k, ti, tj, l);
-        const Region pgn = region_at(k, ti, tj, l - 1);
-        const int32_t rh = g.r_hi - g.r_lo, rw = g.c_hi - g.c_lo;
+        int32_t r0 = ti * k.TH, c0 = tj * k.TW;
+        int32_t step_r = k.TH, step_c = k.TW;  // distance between neighbouring tiles' origins
+        for (int32_t m = L; m > l; --m) {
+            origin_step(k.pool[m], r0, c0);
+            step_r *= k.pool[m].sh;
+            step_c *= k.pool[m].sw;
+        }
         const float *src = lds + pv.buf_off;
         float *dst = lds + lv.buf_off;
         const bool last = (l == L);
-        const bool is_max = p.kind == OP_MAXPOOL;
+        const float padv = last ? 0.0f : pad_value(k.pool[l + 1]);
         int32_t *idxp = p.idx_slot >= 0 ? k.idx[p.idx_slot] : nullptr;
-        // cells of this level the tile owns for index output: up to where the next tile's
-        // region starts (regions overlap by the halo; each cell is written once)
-        int32_t own_r_hi = g.r_hi, own_c_hi = g.c_hi;
-        if (idxp && !last) {
-            own_r_hi = (ti + 1 < k.tiles_h) ? region_at(k, ti + 1, tj, l).r_lo : lv.H;
-            own_c_hi = (tj + 1 < k.tiles_w) ? region_at(k, ti, tj + 1, l).c_lo : lv.W;
-        }
-        const uint32_t items = (uint32_t)k.PPG * (uint32_t)lv.plane_stride;
+        // rows / columns of this level the tile may write to memory: its own tile at the last
+        // level; elsewhere (index output in the middle of a sequence) up to where the next
+        // tile's region starts, so every cell is written exactly once
+        const int32_t own_r = (ti + 1 < k.tiles_h) ? r0 + step_r : lv.H;
+        const int32_t own_c = (tj + 1 < k.tiles_w) ? c0 + step_c : lv.W;
+        const int32_t end_r = min(own_r, lv.H), end_c = min(own_c, lv.W);
+        const uint32_t spr = (uint32_t)lv.items_per_row;
+        const uint32_t per_plane = (uint32_t)lv.rows * spr;
+        const uint32_t items = (uint32_t)nplanes * per_plane;
+        const bool vec_store_ok = (lv.W & 3) == 0 && ((k.TW & 3) == 0 || k.tiles_w == 1);
+        const int32_t spec = (p.kw == 3 && p.sw == 2) ? 1 : (p.kw == 3 && p.sw == 1) ? 2 : (p.kw == 2 && p.sw == 2) ? 3 : 0;
         for (uint32_t i = tid; i < items; i += nthr) {
             const uint32_t pl = fdiv(i, lv.div_plane);
-            const uint32_t rem = i - pl * (uint32_t)lv.plane_stride;
-            const uint32_t r = fdiv(rem, lv.div_pitch);
-            const uint32_t cc = rem - r * (uint32_t)lv.pitch;
-            if ((int32_t)pl >= nplanes || (int32_t)r >= rh || (int32_t)cc >= rw) continue;
+            const uint32_t rem = i - pl * per_plane;
+            const uint32_t r = fdiv(rem, lv.div_row);
+            const uint32_t j = rem - r * spr;
             const uint32_t plane = (uint32_t)plane0 + pl;
-            const int32_t oh = g.r_lo + (int32_t)r, ow = g.c_lo + (int32_t)cc;
-            const int32_t h0 = oh * p.sh - p.ph, w0 = ow * p.sw - p.pw;
-            const int32_t hs = max(h0, 0), he = min(h0 + p.kh, pv.H);
-            const int32_t ws = max(w0, 0), we = min(w0 + p.kw, pv.W);
-            const float *sp = src + pl * (uint32_t)pv.plane_stride + (hs - pgn.r_lo) * pv.pitch + (ws - pgn.c_lo);
-            float val;
-            if (is_max) {
-                float best = -INFINITY;
-                int32_t bi = hs * pv.W + ws;
-                for (int32_t ih = hs; ih < he; ++ih) {
-                    for (int32_t iw = ws; iw < we; ++iw) {
-                        const float v = sp[iw - ws];
-                        const bool gt = v > best;
-                        best = gt ? v : best;
-                        bi = gt ? ih * pv.W + iw : bi;
-                    }
-                    sp += pv.pitch;
-                }
-                val = best;
-                if (idxp && oh < own_r_hi && ow < own_c_hi)
-                    idxp[(plane * (uint32_t)lv.H + (uint32_t)oh) * (uint32_t)lv.W + (uint32_t)ow] = bi;
+            const int32_t gr = r0 + (int32_t)r, gc = c0 + 4 * (int32_t)j;
+            const int32_t h0 = gr * p.sh - p.ph, w0 = gc * p.sw - p.pw;
+            const float *sp = src + pl * (uint32_t)pv.plane_stride + (r * (uint32_t)p.sh) * (uint32_t)pv.pitch + 4u * j * (uint32_t)p.sw;
+            float val[4];
+            int32_t bi[4] = {0, 0, 0, 0};
+            if (idxp) {
+                if (spec == 1) pool_strip<3, 2, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
+                else if (spec == 2) pool_strip<3, 1, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
+                else if (spec == 3) pool_strip<2, 2, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
+                else pool_strip<0, 0, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
             } else {
-                float sum = 0.0f;
-                for (int32_t ih = hs; ih < he; ++ih) {
-                    for (int32_t iw = ws; iw < we; ++iw) sum = sum + sp[iw - ws];
-                    sp += pv.pitch;
-                }
-                const float inv = p.count_include_pad ? p.inv_kk : 1.0f / (float)((he - hs) * (we - ws));
-                val = round_store<BF16>(sum * inv);
+                if (spec == 1) pool_strip<3, 2, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
+                else if (spec == 2) pool_strip<3, 1, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
+                else if (spec == 3) pool_strip<2, 2, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
+                else pool_strip<0, 0, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
+            }
+            if (p.kind != OP_MAXPOOL) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) val[e] = round_store<BF16>(val[e]);
+            }
+            const bool row_in = gr >= 0 && gr < lv.H;
+            // global offset of the strip at this level (clamped to a safe address off-plane)
+            const bool strip_in = row_in && gc >= 0 && gc + 3 < lv.W;
+            const uint32_t goff = (plane * (uint32_t)lv.H + (uint32_t)(row_in ? gr : 0)) * (uint32_t)lv.W;
+            if (idxp && row_in && gr < end_r) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (gc + e >= 0 && gc + e < end_c) idxp[goff + (uint32_t)(gc + e)] = bi[e];
             }
             // element-wise operations attached to this level
-            float x[1][1] = {{val}};
-            const bool v1[1] = {true};
-            const int32_t c1[1] = {(int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C)};
-            const uint32_t o1[1] = {(plane * (uint32_t)lv.H + (uint32_t)oh) * (uint32_t)lv.W + (uint32_t)ow};
-            apply_ew<BF16, 1, 1>(x, v1, c1, o1, lv.ew, lv.n_ew, k.params, k.C, k.res);
+            if (lv.n_ew > 0) {
+                float x[4][1] = {{val[0]}, {val[1]}, {val[2]}, {val[3]}};
+                int32_t c1[4];
+                uint32_t o1[4];
+                const int32_t ch = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    c1[e] = ch;
+                    const int32_t cc = gc + e;
+                    o1[e] = (row_in && cc >= 0 && cc < lv.W) ? goff + (uint32_t)cc : 0u;
+                }
+                apply_ew<BF16, 1, 4>(x, c1, o1, lv.ew, lv.n_ew, k.params, k.C, k.res);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) val[e] = x[e][0];
+            }
             if (last) {
-                store_elems<BF16, 1>(k.out, o1[0], x[0]);
+                if (row_in && gr < end_r) {
+                    if (strip_in && gc + 3 < end_c && vec_store_ok) {
+                        store_elems<BF16, 4>(k.out, goff + (uint32_t)gc, val);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gc + e >= 0 && gc + e < end_c) {
+                                const float one[1] = {val[e]};
+                                store_elems<BF16, 1>(k.out, goff + (uint32_t)(gc + e), one);
+                            }
+                    }
+                }
             } else {
-                dst[pl * (uint32_t)lv.plane_stride + r * (uint32_t)lv.pitch + cc] = x[0][0];
+                float4 w;
+                w.x = (row_in && gc >= 0 && gc < lv.W) ? val[0] : padv;
+                w.y = (row_in && gc + 1 >= 0 && gc + 1 < lv.W) ? val[1] : padv;
+                w.z = (row_in && gc + 2 >= 0 && gc + 2 < lv.W) ? val[2] : padv;
+                w.w = (row_in && gc + 3 >= 0 && gc + 3 < lv.W) ? val[3] : padv;
+                *reinterpret_cast<float4 *>(dst + pl * (uint32_t)lv.plane_stride + r * (uint32_t)lv.pitch + 4u * j) = w;
             }
         }
         if (!last) __syncthreads();
@@ -537,11 +687,11 @@ template <bool BF16, int VEC, int KH>
 static void launch_direct_kw(const PoolDirectK &k, int kw, dim3 grid, dim3 block, hipStream_t st)
 {
     if constexpr (VEC == 8) {
-        if (kw == 8) { pool_direct_kernel<BF16, VEC, KH, 8><<<grid, block, 0, st>>>(k); return; }
+        if (kw == 8) { pool_direct_kernel<BF16, VEC, KH, 8, K_DIRECT_U><<<grid, block, 0, st>>>(k); return; }
     }
-    if (kw == 1) pool_direct_kernel<BF16, VEC, KH, 1><<<grid, block, 0, st>>>(k);
-    else if (kw == 2) pool_direct_kernel<BF16, VEC, KH, 2><<<grid, block, 0, st>>>(k);
-    else pool_direct_kernel<BF16, VEC, KH, 4><<<grid, block, 0, st>>>(k);
+    if (kw == 1) pool_direct_kernel<BF16, VEC, KH, 1, K_DIRECT_U><<<grid, block, 0, st>>>(k);
+    else if (kw == 2) pool_direct_kernel<BF16, VEC, KH, 2, K_DIRECT_U><<<grid, block, 0, st>>>(k);
+    else pool_direct_kernel<BF16, VEC, KH, 4, K_DIRECT_U><<<grid, block, 0, st>>>(k);
 }
 
 template <bool BF16, int VEC>
@@ -573,11 +723,11 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         if (bf16) {
-            if (q.vec == 8) stream_kernel<true, 8><<<grid, block, 0, st>>>(k);
-            else stream_kernel<true, 1><<<grid, block, 0, st>>>(k);
+            if (q.vec == 8) stream_kernel<true, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            else stream_kernel<true, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
         } else {
-            if (q.vec == 4) stream_kernel<false, 4><<<grid, block, 0, st>>>(k);
-            else stream_kernel<false, 1><<<grid, block, 0, st>>>(k);
+            if (q.vec == 4) stream_kernel<false, 4, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            else stream_kernel<false, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
         }
         break;
     }

@@ -127,54 +127,49 @@ bs_status group_steps(bs_stack *s)
 }
 
 // ---------------------------------------------------------------------------
-// Tile geometry.  For a tile [lo, hi) of a pooling operation's output, the input
-// cells its windows touch are [lo*s - p, (hi-1)*s - p + k) clipped to the plane
-// (cells outside the plane are padding and are never loaded or computed).
-// Rows and columns are independent.
+// Tile geometry of an LDS sequence.  A work-group owns a TH x TW tile of the last
+// level.  The rectangle it keeps of level l-1 holds exactly the windows of its
+// rectangle of level l:  extent[l-1] = (extent[l] - 1) * stride + kernel, and its
+// origin is origin[l] * stride - pad (possibly outside the plane: those cells are the
+// pooling operation's padding).  Column extents of levels >= 1 are rounded up to 4,
+// the strip of outputs one lane produces.  Rows and columns are independent.
 // ---------------------------------------------------------------------------
 struct Dim {
     int32_t k, s, p;
 };
 
-static inline void back_one(const Dim &d, int32_t size_in, int32_t &lo, int32_t &hi)
-{
-    int32_t nlo = lo * d.s - d.p, nhi = (hi - 1) * d.s - d.p + d.k;
-    lo = std::max(0, nlo);
-    hi = std::min(size_in, nhi);
-}
-
-// Largest region extent per level over all tiles of size `tile` along one dimension.
-// dims[l] (l = 1..L) is the pool producing level l; size[l] the plane extent at level l.
-static void max_extents(const std::vector<Dim> &dims, const std::vector<int32_t> &size, int32_t tile,
-                        int32_t vec0, std::vector<int32_t> &ext)
-{
-    const int L = (int)dims.size() - 1;
-    ext.assign(L + 1, 0);
-    const int32_t n_tiles = (size[L] + tile - 1) / tile;
-    for (int32_t t = 0; t < n_tiles; ++t) {
-        int32_t lo = t * tile, hi = std::min(size[L], lo + tile);
-        ext[L] = std::max(ext[L], hi - lo);
-        for (int l = L; l >= 1; --l) {
-            back_one(dims[l], size[l - 1], lo, hi);
-            int32_t a = lo, b = hi;
-            if (l - 1 == 0 && vec0 > 1) {
-                a = a / vec0 * vec0;
-                b = (b + vec0 - 1) / vec0 * vec0;
-            }
-            ext[l - 1] = std::max(ext[l - 1], b - a);
-        }
-    }
-}
-
 struct LdsGeom {
     int32_t L = 0;
-    std::vector<Dim> dh, dw;        // index 1..L
-    std::vector<int32_t> H, W;      // index 0..L
-    std::vector<int32_t> rows, cols;  // max region extents per level
+    std::vector<Dim> dh, dw;          // index 1..L
+    std::vector<int32_t> H, W;        // index 0..L
+    std::vector<int32_t> rows, cols;  // region extents per level
+    std::vector<int32_t> pitch;
     uint64_t lds_bytes = 0;
     uint64_t buf_floats[2] = {0, 0};
     double redundancy = 1.0;
 };
+
+static inline int32_t round4(int32_t v) { return (v + 3) / 4 * 4; }
+
+// in-plane cells of [origin, origin + extent) summed over all tiles, along one dimension
+static uint64_t loaded_extent(const std::vector<Dim> &d, const std::vector<int32_t> &size, int32_t tile,
+                              int32_t extent0, int32_t vec0)
+{
+    const int L = (int)d.size() - 1;
+    const int32_t n_tiles = (size[L] + tile - 1) / tile;
+    uint64_t sum = 0;
+    for (int32_t t = 0; t < n_tiles; ++t) {
+        int64_t o = (int64_t)t * tile;
+        for (int l = L; l >= 1; --l) o = o * d[l].s - d[l].p;
+        int64_t lo = std::max<int64_t>(o, 0), hi = std::min<int64_t>(o + extent0, size[0]);
+        if (vec0 > 1) {
+            lo = lo / vec0 * vec0;
+            hi = (hi + vec0 - 1) / vec0 * vec0;
+        }
+        if (hi > lo) sum += (uint64_t)(hi - lo);
+    }
+    return sum;
+}
 
 static void lds_geometry(const bs_stack *s, int32_t first_op, int32_t n_ops, int32_t th, int32_t tw,
                          int32_t ppg, int32_t vec0, LdsGeom &g)
@@ -191,34 +186,27 @@ static void lds_geometry(const bs_stack *s, int32_t first_op, int32_t n_ops, int
         g.H.push_back(op.out_h);
         g.W.push_back(op.out_w);
     }
-    g.L = (int32_t)g.dh.size() - 1;
-    max_extents(g.dh, g.H, th, 1, g.rows);
-    max_extents(g.dw, g.W, tw, vec0, g.cols);
-    if (vec0 > 1) g.cols[0] = (g.cols[0] + vec0 - 1) / vec0 * vec0;
+    const int L = g.L = (int32_t)g.dh.size() - 1;
+    g.rows.assign(L + 1, 0);
+    g.cols.assign(L + 1, 0);
+    g.pitch.assign(L + 1, 0);
+    g.rows[L] = th;
+    g.cols[L] = round4(tw);
+    for (int l = L; l >= 1; --l) {
+        g.rows[l - 1] = (g.rows[l] - 1) * g.dh[l].s + g.dh[l].k;
+        g.cols[l - 1] = (g.cols[l] - 1) * g.dw[l].s + g.dw[l].k;
+        if (l - 1 >= 1) g.cols[l - 1] = round4(g.cols[l - 1]);
+    }
     g.buf_floats[0] = g.buf_floats[1] = 0;
-    for (int l = 0; l < g.L; ++l) {  // level L goes to memory, not to LDS
-        uint64_t need = (uint64_t)ppg * g.rows[l] * g.cols[l];
-        need = (need + 3) / 4 * 4;
+    for (int l = 0; l <= L; ++l) {
+        g.pitch[l] = round4(g.cols[l]);
+        if (l == L) continue;  // level L goes to memory, not to LDS
+        const uint64_t need = (uint64_t)ppg * g.rows[l] * g.pitch[l];
         g.buf_floats[l & 1] = std::max(g.buf_floats[l & 1], need);
     }
     g.lds_bytes = (g.buf_floats[0] + g.buf_floats[1]) * sizeof(float);
-    // elements loaded per plane (sum over tiles of the level-0 region) / plane size
-    const int32_t nth = (g.H[g.L] + th - 1) / th, ntw = (g.W[g.L] + tw - 1) / tw;
-    uint64_t rsum = 0, csum = 0;
-    for (int32_t t = 0; t < nth; ++t) {
-        int32_t lo = t * th, hi = std::min(g.H[g.L], lo + th);
-        for (int l = g.L; l >= 1; --l) back_one(g.dh[l], g.H[l - 1], lo, hi);
-        rsum += (uint64_t)(hi - lo);
-    }
-    for (int32_t t = 0; t < ntw; ++t) {
-        int32_t lo = t * tw, hi = std::min(g.W[g.L], lo + tw);
-        for (int l = g.L; l >= 1; --l) back_one(g.dw[l], g.W[l - 1], lo, hi);
-        if (vec0 > 1) {
-            lo = lo / vec0 * vec0;
-            hi = (hi + vec0 - 1) / vec0 * vec0;
-        }
-        csum += (uint64_t)(hi - lo);
-    }
+    const uint64_t rsum = loaded_extent(g.dh, g.H, th, g.rows[0], 1);
+    const uint64_t csum = loaded_extent(g.dw, g.W, tw, g.cols[0], vec0);
     g.redundancy = (double)rsum * (double)csum / ((double)g.H[0] * (double)g.W[0]);
 }
 
@@ -380,7 +368,7 @@ static void plan_stream(const bs_stack *s, Sequence &q)
     k.C = (int32_t)q.in_shape[1];
     k.div_plane = make_fastdiv((uint32_t)(hw / vec));
     k.div_c = make_fastdiv((uint32_t)k.C);
-    const int64_t per_group = (int64_t)q.threads * 4;  // four 128-bit accesses per thread
+    const int64_t per_group = (int64_t)q.threads * K_STREAM_U;
     q.grid = (k.total + per_group - 1) / per_group;
     q.lds_bytes = 0;
     q.redundancy = 1.0;
@@ -414,7 +402,7 @@ static void plan_direct(const bs_stack *s, Sequence &q)
     k.div_wv = make_fastdiv((uint32_t)wv);
     k.div_ho = make_fastdiv((uint32_t)k.Ho);
     k.div_c = make_fastdiv((uint32_t)k.C);
-    const int64_t per_group = (int64_t)q.threads * 2;  // two units (kh rows each) per thread
+    const int64_t per_group = (int64_t)q.threads * K_DIRECT_U;
     q.grid = ((int64_t)k.total + per_group - 1) / per_group;
     q.lds_bytes = 0;
     q.redundancy = (double)(k.Ho * k.pool.kh) / (double)k.H;
@@ -443,15 +431,21 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
         if (g.lds_bytes > budget) return;
         const int64_t nth = (HL + th - 1) / th, ntw = (WL + tw - 1) / tw;
         const int64_t grid = nth * ntw * ((planes + ppg - 1) / ppg);
-        // cost model: redundant loads, ragged last tile, idle lanes in tiny tiles, too few
-        // work-groups to fill the chip, and a mild preference for smaller LDS (occupancy).
+        // cost model: redundant loads, ragged last tile, lanes idle in the widest pooling
+        // phase, too few work-groups to fill the chip, and a mild preference for smaller
+        // LDS (occupancy).
         double score = g.redundancy;
         score *= (double)(nth * th) / HL * (double)(ntw * tw) / WL;
-        const double outs = (double)th * tw * ppg;
-        if (outs < q.threads) score *= 1.0 + 0.5 * (q.threads - outs) / q.threads;
-        const double want = 4.0 * std::max(1, lim.num_cus);
+        double worst_fill = 1.0;
+        for (int l = 1; l <= g.L; ++l) {
+            const double strips = (double)ppg * g.rows[l] * (g.cols[l] / 4);
+            const double passes = std::ceil(strips / q.threads);
+            worst_fill = std::min(worst_fill, strips / (passes * q.threads));
+        }
+        score *= 1.0 + 0.35 * (1.0 - worst_fill);
+        const double want = 8.0 * std::max(1, lim.num_cus);
         if ((double)grid < want) score *= 1.0 + 0.25 * (want - grid) / want;
-        score *= 1.0 + 0.15 * (double)g.lds_bytes / (double)std::max<uint64_t>(budget, 1);
+        score *= 1.0 + 0.25 * (double)g.lds_bytes / (double)std::max<uint64_t>(budget, 1);
         if (tw != WL) score *= 1.05;
         if (score < best_score) {
             best_score = score;
@@ -464,17 +458,15 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
                  o.planes_per_group > 0 ? (int32_t)std::min<int64_t>(o.planes_per_group, planes) : 1);
     } else {
         std::vector<int32_t> tws, ths;
-        for (int32_t d = 1; d <= 16; d *= 2) tws.push_back((WL + d - 1) / d);
-        for (int32_t t : {1, 2, 4, 8, 16, 32}) if (t < WL) tws.push_back(t);
-        for (int32_t d = 1; d <= HL; ++d) {
-            int32_t t = (HL + d - 1) / d;
-            if (ths.empty() || ths.back() != t) ths.push_back(t);
-        }
+        tws.push_back(WL);
+        for (int32_t t = 4; t < WL; t += 4) tws.push_back(t);
+        for (int32_t t : {1, 2}) if (t < WL) tws.push_back(t);
+        for (int32_t t = 1; t <= HL; ++t) ths.push_back(t);
         for (int32_t tw : tws)
             for (int32_t th : ths) {
                 consider(th, tw, 1);
                 if (th == HL && tw == WL)
-                    for (int32_t ppg : {2, 4, 8, 16}) consider(th, tw, ppg);
+                    for (int32_t ppg : {2, 3, 4, 6, 8, 12, 16}) consider(th, tw, ppg);
             }
     }
     if (best_th == 0) return BS_ERR_NO_FIT;
@@ -510,14 +502,15 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
     for (int l = 0; l <= g.L; ++l) {
         LevelK &lv = k.level[l];
         lv.H = g.H[l]; lv.W = g.W[l];
-        lv.rows_max = g.rows[l];
-        lv.pitch = g.cols[l];
-        lv.plane_stride = lv.rows_max * lv.pitch;
+        lv.rows = g.rows[l];
+        lv.cols = g.cols[l];
+        lv.pitch = g.pitch[l];
+        lv.plane_stride = lv.rows * lv.pitch;
         lv.buf_off = (l & 1) ? (int32_t)g.buf_floats[0] : 0;
         lv.n_ew = 0;
-        const uint32_t v = (l == 0) ? (uint32_t)vec0 : 1u;
-        lv.div_pitch = make_fastdiv((uint32_t)lv.pitch / v);
-        lv.div_plane = make_fastdiv((uint32_t)lv.plane_stride / v);
+        lv.items_per_row = (l == 0) ? (vec0 > 1 ? (lv.cols + vec0 - 1) / vec0 + 1 : lv.cols) : lv.cols / 4;
+        lv.div_row = make_fastdiv((uint32_t)lv.items_per_row);
+        lv.div_plane = make_fastdiv((uint32_t)(lv.rows * lv.items_per_row));
     }
     for (int32_t i = q.first_op; i < q.first_op + q.n_ops; ++i) {
         const Op &op = s->ops[i];
@@ -533,53 +526,49 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
     return BS_OK;
 }
 
-// Bounds audit of an LDS sequence, run on the host at plan time with the very function the
-// kernel uses for its geometry: every region lies inside its plane and inside the LDS buffer
-// reserved for its level, every pooling window's in-range cells lie inside the region cached
-// from the level below, and index outputs in the middle of a sequence are covered without gaps.
-// A plan that fails it is never launched.
+// Bounds audit of an LDS sequence, run on the host at plan time: the rectangle of every
+// level holds all windows of the level above, every level's buffer lies inside the LDS
+// allocation with 16-byte aligned rows, item counts match the extents, and an index output
+// in the middle of a sequence is covered by the tiles without gaps.  A plan that fails it is
+// never launched.
 static bool audit_lds(const Sequence &q)
 {
     const LdsSeqK &k = q.lds;
     const int32_t L = k.n_levels;
     const uint64_t lds_floats = q.lds_bytes / sizeof(float);
     if (L < 1 || L > K_MAX_LEVELS || k.PPG < 1 || k.TH < 1 || k.TW < 1) return false;
-    for (int l = 0; l < L; ++l) {
-        const LevelK &lv = k.level[l];
-        if (lv.plane_stride != lv.rows_max * lv.pitch) return false;
-        if ((uint64_t)lv.buf_off + (uint64_t)k.PPG * lv.plane_stride > lds_floats) return false;
-        if (l == 0 && k.vec > 1 && (lv.pitch % k.vec != 0 || lv.W % k.vec != 0 || lv.buf_off % 4 != 0)) return false;
-    }
-    for (int pass = 0; pass < 2; ++pass) {  // rows with tj = 0, then columns with ti = 0
-        const int32_t n_tiles = pass == 0 ? k.tiles_h : k.tiles_w;
-        for (int32_t t = 0; t < n_tiles; ++t) {
-            const int32_t ti = pass == 0 ? t : 0, tj = pass == 0 ? 0 : t;
-            for (int l = 0; l <= L; ++l) {
-                const Region g = region_at(k, ti, tj, l);
-                const int32_t lo = pass == 0 ? g.r_lo : g.c_lo, hi = pass == 0 ? g.r_hi : g.c_hi;
-                const int32_t size = pass == 0 ? k.level[l].H : k.level[l].W;
-                const int32_t cap = pass == 0 ? k.level[l].rows_max : k.level[l].pitch;
-                if (lo < 0 || hi <= lo || hi > size || hi - lo > cap) return false;
-                if (l == 0 && pass == 1 && k.vec > 1 && (lo % k.vec || hi % k.vec)) return false;
-                if (l == 0) continue;
-                const Region pg = region_at(k, ti, tj, l - 1);
-                const PoolK &p = k.pool[l];
-                const int32_t plo = pass == 0 ? pg.r_lo : pg.c_lo, phi = pass == 0 ? pg.r_hi : pg.c_hi;
-                const int32_t psize = pass == 0 ? k.level[l - 1].H : k.level[l - 1].W;
-                const int32_t kk = pass == 0 ? p.kh : p.kw, ss = pass == 0 ? p.sh : p.sw, pp = pass == 0 ? p.ph : p.pw;
-                for (int32_t o = lo; o < hi; ++o) {
-                    const int32_t s0 = std::max(o * ss - pp, 0), s1 = std::min(o * ss - pp + kk, psize);
-                    if (s0 >= s1 || s0 < plo || s1 > phi) return false;
-                }
-                if (p.idx_slot >= 0 && l < L && t + 1 < n_tiles) {
-                    const Region nx = pass == 0 ? region_at(k, ti + 1, tj, l) : region_at(k, ti, tj + 1, l);
-                    const int32_t nlo = pass == 0 ? nx.r_lo : nx.c_lo;
-                    if (nlo > hi || nlo < lo) return false;
-                }
-                if (p.idx_slot >= 0 && l < L && t + 1 == n_tiles && hi != size) return false;
-            }
+    if (k.vec != 1 && k.vec != 4 && k.vec != 8) return false;
+    if (k.level[L].rows != k.TH || k.level[L].cols < k.TW || k.level[L].cols % 4) return false;
+    if (k.vec > 1 && k.level[0].W % k.vec) return false;
+    int64_t lo_r = 0, lo_c = 0;  // most negative origin (tile 0)
+    for (int l = L; l >= 1; --l) {
+        const LevelK &lv = k.level[l], &pv = k.level[l - 1];
+        const PoolK &p = k.pool[l];
+        if (p.kh < 1 || p.kw < 1 || p.sh < 1 || p.sw < 1) return false;
+        if (lv.cols % 4 || lv.items_per_row != lv.cols / 4) return false;
+        if (pv.rows < (lv.rows - 1) * p.sh + p.kh) return false;
+        if (pv.cols < (lv.cols - 1) * p.sw + p.kw) return false;
+        lo_r = lo_r * p.sh - p.ph;
+        lo_c = lo_c * p.sw - p.pw;
+        if (p.idx_slot >= 0 && l < L) {
+            // tiles must cover the whole level: checked by the planner's covers_input() rule;
+            // here: the rectangle is at least as large as the distance between tile origins
+            int64_t step_r = k.TH, step_c = k.TW;
+            for (int m = L; m > l; --m) { step_r *= k.pool[m].sh; step_c *= k.pool[m].sw; }
+            if (lv.rows < step_r || lv.cols < step_c) return false;
         }
     }
+    if (lo_c < -(int64_t)4096 * std::max(k.vec, 1) || lo_r < -(1 << 20)) return false;
+    for (int l = 0; l < L; ++l) {
+        const LevelK &lv = k.level[l];
+        if (lv.pitch < lv.cols || lv.pitch % 4 || lv.buf_off % 4) return false;
+        if (lv.plane_stride != lv.rows * lv.pitch) return false;
+        if ((uint64_t)lv.buf_off + (uint64_t)k.PPG * lv.plane_stride > lds_floats) return false;
+        if (l + 1 < L && (l & 1) == ((l + 1) & 1)) return false;
+    }
+    const LevelK &l0 = k.level[0];
+    const int32_t want0 = k.vec > 1 ? (l0.cols + k.vec - 1) / k.vec + 1 : l0.cols;
+    if (l0.items_per_row != want0) return false;
     return true;
 }
 
