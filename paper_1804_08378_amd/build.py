@@ -15,6 +15,9 @@ SOURCES = ["bs_stack.cpp", "bs_plan.cpp", "bs_run.cpp", "bs_kernels.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
          "-fno-fast-math", "-fvisibility=hidden", "-Wall", "-Wextra", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the by-value kernel argument blocks are read in place (kernarg segment) only if the
+         # optimizer may look through all their uses; the default cap is too low for the LDS kernel
+         "-mllvm", "-instcombine-max-copied-from-constant-users=100000",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

@@ -83,8 +83,9 @@ struct LevelK {
     int32_t n_ew;
     EwOp ew[K_MAX_EW];       // applied to a value once it exists at this level
     int32_t items_per_row;   // level 0: global vectors per region row; else strips of 4 outputs
-    FastDiv div_row;         // by items_per_row
-    FastDiv div_plane;       // by rows * items_per_row
+    int32_t ct, rt;          // lane grid of a phase: ct = min(items_per_row, threads) lanes along a
+                             // row, rt = threads / ct rows in flight
+    FastDiv div_ct;          // by ct
 };
 
 struct LdsSeqK {
@@ -97,6 +98,8 @@ struct LdsSeqK {
     int32_t NC, C;
     int32_t TH, TW, tiles_h, tiles_w, PPG;
     int32_t vec;       // elements per 128-bit access used for the level-0 load (1 = scalar)
+    int32_t delta0;    // level-0 LDS column of the region's first column: the LDS row starts at the
+                       // 128-bit global vector that contains it (0 when vec == 1)
     FastDiv div_tiles_w, div_tiles_hw, div_c;
     LevelK level[K_MAX_LEVELS + 1];
     PoolK pool[K_MAX_LEVELS + 1];  // pool[l] produces level l from level l-1 (l >= 1)

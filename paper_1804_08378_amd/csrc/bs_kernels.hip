@@ -172,7 +172,7 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = x[u][i] > 0.0f ? x[u][i] : 0.0f;
+                for (int i = 0; i < VEC; ++i) x[u][i] = __builtin_fmaxf(x[u][i], 0.0f);  // NaN, -0 -> +0
         } else {  // OP_ADD
             const void *rp = res[arg];
             Raw<BF16, VEC> rr[U];
@@ -299,8 +299,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
                     for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
                         for (int dw = 0; dw < KW; ++dw) {
-                            const float v = x[dh][j * KW + dw];
-                            best = v > best ? v : best;
+                            best = __builtin_fmaxf(best, x[dh][j * KW + dw]);
                         }
                     y[u][j] = best;
                     yi[u][j] = 0;
@@ -351,12 +350,79 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 // +0 is never -0).  They are never computed from earlier layers.  Level l (l < L) lives in
 // LDS buffer l & 1; a barrier separates the phases (Section 4.4's two-buffer scheme).
 //
-// Phase 0 loads 128-bit global vectors and scatters them to LDS after the level-0
-// element-wise operations.  Phase l gives each lane a strip of four horizontally adjacent
-// outputs: it reads the kh rows x (3*sw + kw) columns it needs with 128/64/32-bit LDS reads
-// (strip starts are 16-byte aligned by construction) and keeps the windows in registers.
+// Lane grid.  In every phase the work-group's lanes form a ct x rt grid (one division per
+// lane per phase): ct lanes along a row, rt rows in flight; a lane keeps its column and
+// walks down the rows, so all column arithmetic and predicates are loop-invariant and the
+// plane (hence the BatchNorm channel) is uniform per iteration: folded parameters are read
+// with scalar loads.
+//
+// Phase 0 loads 128-bit global vectors and stores them with one 128-bit LDS write each,
+// after the level-0 element-wise operations: the level-0 LDS row starts at the global
+// vector that contains the rectangle's first column (D = delta0 columns earlier).
+// Phase l gives each lane a strip of four horizontally adjacent outputs: it reads the
+// kh rows x (D + 3*sw + kw) columns it needs with aligned 128/64/32-bit LDS reads and keeps
+// the windows in registers.
 // =============================================================================
 BS_DEV float pad_value(const PoolK &p) { return p.kind == OP_MAXPOOL ? -INFINITY : 0.0f; }
+
+typedef const __attribute__((address_space(4))) float *const_f32_ptr;
+
+// Folded BatchNorm parameters of one level for one (uniform) channel, fetched with scalar loads.
+struct EwRegs {
+    float sc[K_MAX_EW], sh[K_MAX_EW];
+};
+
+BS_DEV void load_ew_regs(const LevelK &lv, const float *params, int32_t C, int32_t c, EwRegs &e)
+{
+    const_f32_ptr cp = (const_f32_ptr)params;
+#pragma unroll
+    for (int j = 0; j < K_MAX_EW; ++j) {
+        e.sc[j] = 1.0f;
+        e.sh[j] = 0.0f;
+        if (j < lv.n_ew && lv.ew[j].kind == OP_BN) {
+            e.sc[j] = cp[lv.ew[j].arg + c];
+            e.sh[j] = cp[lv.ew[j].arg + C + c];
+        }
+    }
+}
+
+// Element-wise operations of a level on N values of one plane.  contiguous: the N values are
+// consecutive elements starting at off[0] (one vector residual load); else off[i] each.
+template <bool BF16, int N, bool CONTIG>
+BS_DEV void apply_level_ew(float (&x)[N], const LevelK &lv, const EwRegs &er, const void *const *res,
+                           const uint32_t (&off)[CONTIG ? 1 : N])
+{
+#pragma unroll
+    for (int j = 0; j < K_MAX_EW; ++j) {
+        if (j >= lv.n_ew) break;
+        const int32_t kind = lv.ew[j].kind;
+        if (kind == OP_BN) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fmaf(x[i], er.sc[j], er.sh[j]));
+        } else if (kind == OP_RELU) {
+            // v_max_f32: NaN -> 0, and max(-0, +0) = +0 in either operand order
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = __builtin_fmaxf(x[i], 0.0f);
+        } else {
+            const void *rp = res[lv.ew[j].arg];
+            float r[N];
+            if constexpr (CONTIG) {
+                const Raw<BF16, N> rr = load_raw<BF16, N>(rp, off[0]);
+                unpack<BF16, N>(rr, r);
+            } else {
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    const Raw<BF16, 1> rr = load_raw<BF16, 1>(rp, off[i]);
+                    float one[1];
+                    unpack<BF16, 1>(rr, one);
+                    r[i] = one[0];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(x[i] + r[i]);
+        }
+    }
+}
 
 // Read N consecutive floats starting at a 16-byte aligned LDS address.
 template <int N>
@@ -377,90 +443,195 @@ BS_DEV void lds_read_row(const float *p, float (&r)[N])
 }
 
 // One strip of four outputs of pooling operation p from the cached level below.
-//   src      first cell of the strip's first window (row r*sh, column 4*j*sw of the region)
-//   h0, w0   global row / column of that cell in the input plane (may be negative: padding)
-// KW/SW > 0: compile-time window width / stride; 0: run-time (scalar reads).
-template <int KW, int SW, bool WANT_IDX>
-BS_DEV void pool_strip(const PoolK &p, const float *src, int32_t pitch, int32_t h0, int32_t w0,
+//   src      16-byte aligned LDS address; the strip's first window starts D floats after it
+//   h0, w0   global row / column of the first window's first cell in the input plane (may be
+//            negative: padding)
+// KH/KW/SW > 0: compile-time window and stride (D < 4); KH == 0: run-time shape, scalar reads.
+template <int KH, int KW, int SW, int D, bool WANT_IDX>
+BS_DEV void pool_strip(const PoolK &p, const float *src, int32_t d_rt, int32_t pitch, int32_t h0, int32_t w0,
                        int32_t Hp, int32_t Wp, float (&val)[4], int32_t (&bidx)[4])
 {
     const bool is_max = p.kind == OP_MAXPOOL;
-    const int32_t kw = KW > 0 ? KW : p.kw, sw = SW > 0 ? SW : p.sw;
-    if (is_max) {
-        float best[4];
+    const int32_t kh = KH > 0 ? KH : p.kh, kw = KH > 0 ? KW : p.kw, sw = KH > 0 ? SW : p.sw;
+    constexpr int NC = 3 * SW + KW;                           // columns four windows span
+    constexpr int NR = KH > 0 ? (D == 0 ? NC : (D + NC + 3) / 4 * 4) : 1;  // floats read per row
+    float acc[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            best[e] = -INFINITY;
-            if constexpr (WANT_IDX) bidx[e] = max(h0, 0) * Wp + max(w0 + e * sw, 0);  // first in-range cell
-        }
-        for (int32_t dh = 0; dh < p.kh; ++dh) {
-            const float *rowp = src + dh * pitch;
-            const int32_t rbase = (h0 + dh) * Wp + w0;
-            if constexpr (KW > 0) {
-                constexpr int NCOL = 3 * SW + KW;
-                float r[NCOL];
-                lds_read_row<NCOL>(rowp, r);
+    for (int e = 0; e < 4; ++e) {
+        acc[e] = is_max ? -INFINITY : 0.0f;
+        if constexpr (WANT_IDX) bidx[e] = max(h0, 0) * Wp + max(w0 + e * sw, 0);  // first in-range cell
+    }
+    if constexpr (KH > 0) {
+        float r[KH][NR];
+#pragma unroll
+        for (int dh = 0; dh < KH; ++dh) lds_read_row<NR>(src + dh * pitch, r[dh]);
+        if (is_max) {
+#pragma unroll
+            for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int dw = 0; dw < KW; ++dw) {
-                        const float v = r[e * SW + dw];
-                        const bool g = v > best[e];
-                        best[e] = g ? v : best[e];
-                        if constexpr (WANT_IDX) bidx[e] = g ? rbase + e * SW + dw : bidx[e];
+                        const float v = r[dh][D + e * SW + dw];
+                        if constexpr (WANT_IDX) {
+                            const bool g = v > acc[e];
+                            acc[e] = g ? v : acc[e];
+                            bidx[e] = g ? (h0 + dh) * Wp + w0 + e * SW + dw : bidx[e];
+                        } else {
+                            acc[e] = __builtin_fmaxf(acc[e], v);
+                        }
                     }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    for (int32_t dw = 0; dw < kw; ++dw) {
-                        const float v = rowp[e * sw + dw];
-                        const bool g = v > best[e];
-                        best[e] = g ? v : best[e];
-                        if constexpr (WANT_IDX) bidx[e] = g ? rbase + e * sw + dw : bidx[e];
-                    }
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) val[e] = best[e];
-    } else {
-        float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int32_t dh = 0; dh < p.kh; ++dh) {
-            const float *rowp = src + dh * pitch;
-            if constexpr (KW > 0) {
-                constexpr int NCOL = 3 * SW + KW;
-                float r[NCOL];
-                lds_read_row<NCOL>(rowp, r);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int dw = 0; dw < KW; ++dw) sum[e] = sum[e] + r[e * SW + dw];
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    for (int32_t dw = 0; dw < kw; ++dw) sum[e] = sum[e] + rowp[e * sw + dw];
-            }
-        }
-        if (p.count_include_pad) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) val[e] = sum[e] * p.inv_kk;
         } else {
-            const int32_t nr = min(h0 + p.kh, Hp) - max(h0, 0);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int32_t we = w0 + e * sw;
-                const int32_t nc = min(we + kw, Wp) - max(we, 0);
-                // cells outside the plane can make nr * nc <= 0; those outputs are never stored
-                val[e] = sum[e] * (1.0f / (float)max(nr * nc, 1));
+            for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw) acc[e] = acc[e] + r[dh][D + e * SW + dw];
+        }
+    } else {
+        for (int32_t dh = 0; dh < kh; ++dh) {
+            const float *rowp = src + dh * pitch + d_rt;
+            const int32_t rbase = (h0 + dh) * Wp + w0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                for (int32_t dw = 0; dw < kw; ++dw) {
+                    const float v = rowp[e * sw + dw];
+                    if (is_max) {
+                        const bool g = v > acc[e];
+                        acc[e] = g ? v : acc[e];
+                        if constexpr (WANT_IDX) bidx[e] = g ? rbase + e * sw + dw : bidx[e];
+                    } else {
+                        acc[e] = acc[e] + v;
+                    }
+                }
+        }
+    }
+    if (is_max) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) val[e] = acc[e];
+    } else if (p.count_include_pad) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) val[e] = acc[e] * p.inv_kk;
+    } else {
+        const int32_t nr = min(h0 + kh, Hp) - max(h0, 0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int32_t we = w0 + e * sw;
+            const int32_t nc = min(we + kw, Wp) - max(we, 0);
+            // windows wholly outside the plane can make nr * nc <= 0; such outputs are never stored
+            val[e] = acc[e] * (1.0f / (float)max(nr * nc, 1));
+        }
+    }
+}
+
+// Everything a pooling phase needs that does not depend on the lane.
+struct PhaseCtx {
+    const float *src;
+    float *dst;
+    int32_t r0, c0;        // global row / column of this level's rectangle origin
+    int32_t end_r, end_c;  // rows / columns below which this tile writes memory at this level
+    int32_t d_lo;          // LDS column of the rectangle's first column in the level below
+    int32_t nplanes, plane0;
+    bool last, vec_store_ok;
+    float padv;
+    int32_t *idxp;
+};
+
+template <bool BF16, int KH, int KW, int SW, int D, bool WANT_IDX>
+BS_DEV void pool_phase(const LdsSeqK &k, const LevelK &lv, const LevelK &pv, const PoolK &p, const PhaseCtx &cx)
+{
+    const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+    const uint32_t ty = fdiv(tid, lv.div_ct), tx = tid - ty * (uint32_t)lv.ct;
+    if ((int32_t)ty >= lv.rt) return;
+    const int32_t spr = lv.items_per_row;
+    for (int32_t pl = 0; pl < cx.nplanes; ++pl) {
+        const uint32_t plane = (uint32_t)(cx.plane0 + pl);
+        const int32_t ch = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+        EwRegs er;
+        load_ew_regs(lv, k.params, k.C, ch, er);
+        const float *splane = cx.src + pl * pv.plane_stride;
+        float *dplane = cx.dst + pl * lv.plane_stride;
+        const uint32_t gplane = plane * (uint32_t)(lv.H * lv.W);
+        for (int32_t j = (int32_t)tx; j < spr; j += lv.ct) {
+            const int32_t gc = cx.c0 + 4 * j;
+            const int32_t w0 = gc * p.sw - p.pw;
+            // aligned LDS column where this strip's reads start; the first window starts D (or,
+            // for run-time shapes, d_rt) floats later
+            const int32_t scol = 4 * j * p.sw + (KH > 0 ? (cx.d_lo - D) : 0);
+            const int32_t d_rt = KH > 0 ? 0 : cx.d_lo;
+            bool cin[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cin[e] = gc + e >= 0 && gc + e < lv.W;
+            const bool strip_vec = cx.vec_store_ok && gc >= 0 && gc + 3 < cx.end_c;
+            for (int32_t r = (int32_t)ty; r < lv.rows; r += lv.rt) {
+                const int32_t gr = cx.r0 + r;
+                const int32_t h0 = gr * p.sh - p.ph;
+                float val[4];
+                int32_t bi[4] = {0, 0, 0, 0};
+                pool_strip<KH, KW, SW, D, WANT_IDX>(p, splane + (r * p.sh) * pv.pitch + scol, d_rt, pv.pitch, h0, w0,
+                                                    pv.H, pv.W, val, bi);
+                if (p.kind != OP_MAXPOOL) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) val[e] = round_store<BF16>(val[e]);
+                }
+                const bool row_in = gr >= 0 && gr < lv.H;
+                const uint32_t goff = gplane + (uint32_t)(row_in ? gr : 0) * (uint32_t)lv.W;
+                if constexpr (WANT_IDX) {
+                    if (row_in && gr < cx.end_r) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (gc + e >= 0 && gc + e < cx.end_c) cx.idxp[goff + (uint32_t)(gc + e)] = bi[e];
+                    }
+                }
+                if (lv.n_ew > 0) {
+                    uint32_t o4[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o4[e] = (row_in && cin[e]) ? goff + (uint32_t)(gc + e) : 0u;
+                    apply_level_ew<BF16, 4, false>(val, lv, er, k.res, o4);
+                }
+                if (cx.last) {
+                    if (row_in && gr < cx.end_r) {
+                        if (strip_vec) {
+                            store_elems<BF16, 4>(k.out, goff + (uint32_t)gc, val);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (gc + e >= 0 && gc + e < cx.end_c) {
+                                    const float one[1] = {val[e]};
+                                    store_elems<BF16, 1>(k.out, goff + (uint32_t)(gc + e), one);
+                                }
+                        }
+                    }
+                } else {
+                    float4 w;
+                    w.x = (row_in && cin[0]) ? val[0] : cx.padv;
+                    w.y = (row_in && cin[1]) ? val[1] : cx.padv;
+                    w.z = (row_in && cin[2]) ? val[2] : cx.padv;
+                    w.w = (row_in && cin[3]) ? val[3] : cx.padv;
+                    *reinterpret_cast<float4 *>(dplane + r * lv.pitch + 4 * j) = w;
+                }
             }
         }
     }
+    (void)nthr;
+}
+
+template <bool BF16, int D, bool WANT_IDX>
+BS_DEV void pool_phase_dispatch(const LdsSeqK &k, const LevelK &lv, const LevelK &pv, const PoolK &p,
+                                const PhaseCtx &cx)
+{
+    if (p.kh == 3 && p.kw == 3 && p.sw == 2) pool_phase<BF16, 3, 3, 2, D, WANT_IDX>(k, lv, pv, p, cx);
+    else if (p.kh == 3 && p.kw == 3 && p.sw == 1) pool_phase<BF16, 3, 3, 1, D, WANT_IDX>(k, lv, pv, p, cx);
+    else if (p.kh == 2 && p.kw == 2 && p.sw == 2) pool_phase<BF16, 2, 2, 2, D, WANT_IDX>(k, lv, pv, p, cx);
+    else pool_phase<BF16, 0, 0, 0, 0, WANT_IDX>(k, lv, pv, p, cx);
 }
 
 template <bool BF16, int VEC>
 __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
 {
     extern __shared__ __align__(16) float lds[];
-    const uint32_t tid = threadIdx.x, nthr = blockDim.x;
+    const uint32_t tid = threadIdx.x;
     const int32_t L = k.n_levels;
 
     // work-group -> (plane group, tile row, tile column)
@@ -477,48 +648,57 @@ __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
         int32_t r0 = ti * k.TH, c0 = tj * k.TW;
         for (int32_t l = L; l >= 1; --l) origin_step(k.pool[l], r0, c0);
         const float padv = pad_value(k.pool[1]);
-        // first global vector column touching the region (floor division of a possibly
-        // negative column)
-        const int32_t gv0 = (c0 + 4096 * VEC) / VEC - 4096;
-        const uint32_t nvr = (uint32_t)lv.items_per_row;
-        const uint32_t per_plane = (uint32_t)lv.rows * nvr;
-        const uint32_t items = (uint32_t)nplanes * per_plane;
-        float *dst = lds + lv.buf_off;
+        const int32_t g0 = c0 - k.delta0;  // global column of LDS column 0: a multiple of VEC
+        const uint32_t ty = fdiv(tid, lv.div_ct), tx = tid - ty * (uint32_t)lv.ct;
+        const bool active = (int32_t)ty < lv.rt;
         constexpr int U = (VEC == 8) ? 2 : 4;
-        for (uint32_t base = tid; base < items; base += nthr * U) {
-            Raw<BF16, VEC> raw[U];
-            bool live[U], inimg[U];
-            uint32_t off[U];
-            int32_t c[U], lrow[U], lcol[U];
+        float *dst = lds + lv.buf_off;
+        for (int32_t pl = 0; pl < nplanes && active; ++pl) {
+            const uint32_t plane = (uint32_t)(plane0 + pl);
+            const int32_t ch = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+            EwRegs er;
+            load_ew_regs(lv, k.params, k.C, ch, er);
+            const uint32_t gplane = plane * (uint32_t)(lv.H * lv.W);
+            float *dplane = dst + pl * lv.plane_stride;
+            for (int32_t v = (int32_t)tx; v < lv.items_per_row; v += lv.ct) {
+                const int32_t gc = g0 + v * VEC;
+                const bool col_in = gc >= 0 && gc < lv.W;  // W % VEC == 0: a vector is all in or all out
+                for (int32_t rb = (int32_t)ty; rb < lv.rows; rb += lv.rt * U) {
+                    Raw<BF16, VEC> raw[U];
+                    bool inimg[U];
+                    uint32_t off[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t i = base + u * nthr;
-                live[u] = i < items;
-                i = live[u] ? i : 0u;
-                const uint32_t pl = fdiv(i, lv.div_plane);
-                const uint32_t rem = i - pl * per_plane;
-                const uint32_t r = fdiv(rem, lv.div_row);
-                const uint32_t v = rem - r * nvr;
-                const int32_t gr = r0 + (int32_t)r, gc = (gv0 + (int32_t)v) * VEC;
-                inimg[u] = gr >= 0 && gr < lv.H && gc >= 0 && gc < lv.W;
-                const uint32_t plane = (uint32_t)plane0 + pl;
-                c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
-                off[u] = inimg[u] ? (plane * (uint32_t)lv.H + (uint32_t)gr) * (uint32_t)lv.W + (uint32_t)gc : 0u;
-                lrow[u] = (int32_t)(pl * (uint32_t)lv.plane_stride + r * (uint32_t)lv.pitch);
-                lcol[u] = gc - c0;
-                raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
-            }
-            float x[U][VEC];
+                    for (int u = 0; u < U; ++u) {
+                        const int32_t r = rb + u * lv.rt;
+                        const int32_t gr = r0 + r;
+                        inimg[u] = col_in && r < lv.rows && gr >= 0 && gr < lv.H;
+                        off[u] = inimg[u] ? gplane + (uint32_t)gr * (uint32_t)lv.W + (uint32_t)gc : 0u;
+                        raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
+                    }
 #pragma unroll
-            for (int u = 0; u < U; ++u) unpack<BF16, VEC>(raw[u], x[u]);
-            apply_ew<BF16, VEC, U>(x, c, off, lv.ew, lv.n_ew, k.params, k.C, k.res);
+                    for (int u = 0; u < U; ++u) {
+                        const int32_t r = rb + u * lv.rt;
+                        float x[VEC];
+                        unpack<BF16, VEC>(raw[u], x);
+                        const uint32_t o1[1] = {off[u]};
+                        apply_level_ew<BF16, VEC, true>(x, lv, er, k.res, o1);
+                        if (r < lv.rows) {
+                            float *d = dplane + r * lv.pitch + v * VEC;
+                            if constexpr (VEC >= 4) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (!live[u]) continue;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    const int32_t lc = lcol[u] + e;
-                    if (lc >= 0 && lc < lv.cols) dst[lrow[u] + lc] = inimg[u] ? x[u][e] : padv;
+                                for (int h = 0; h < VEC / 4; ++h) {
+                                    float4 w;
+                                    w.x = inimg[u] ? x[4 * h] : padv;
+                                    w.y = inimg[u] ? x[4 * h + 1] : padv;
+                                    w.z = inimg[u] ? x[4 * h + 2] : padv;
+                                    w.w = inimg[u] ? x[4 * h + 3] : padv;
+                                    *reinterpret_cast<float4 *>(d + 4 * h) = w;
+                                }
+                            } else {
+                                d[0] = inimg[u] ? x[0] : padv;
+                            }
+                        }
+                    }
                 }
             }
         }
@@ -530,103 +710,44 @@ __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
         const LevelK &lv = k.level[l];
         const LevelK &pv = k.level[l - 1];
         const PoolK &p = k.pool[l];
-        int32_t r0 = ti * k.TH, c0 = tj * k.TW;
+        PhaseCtx cx;
+        cx.r0 = ti * k.TH;
+        cx.c0 = tj * k.TW;
         int32_t step_r = k.TH, step_c = k.TW;  // distance between neighbouring tiles' origins
         for (int32_t m = L; m > l; --m) {
-            origin_step(k.pool[m], r0, c0);
+            origin_step(k.pool[m], cx.r0, cx.c0);
             step_r *= k.pool[m].sh;
             step_c *= k.pool[m].sw;
         }
-        const float *src = lds + pv.buf_off;
-        float *dst = lds + lv.buf_off;
-        const bool last = (l == L);
-        const float padv = last ? 0.0f : pad_value(k.pool[l + 1]);
-        int32_t *idxp = p.idx_slot >= 0 ? k.idx[p.idx_slot] : nullptr;
+        cx.src = lds + pv.buf_off;
+        cx.dst = lds + lv.buf_off;
+        cx.last = (l == L);
+        cx.padv = cx.last ? 0.0f : pad_value(k.pool[l + 1]);
+        cx.idxp = p.idx_slot >= 0 ? k.idx[p.idx_slot] : nullptr;
         // rows / columns of this level the tile may write to memory: its own tile at the last
         // level; elsewhere (index output in the middle of a sequence) up to where the next
-        // tile's region starts, so every cell is written exactly once
-        const int32_t own_r = (ti + 1 < k.tiles_h) ? r0 + step_r : lv.H;
-        const int32_t own_c = (tj + 1 < k.tiles_w) ? c0 + step_c : lv.W;
-        const int32_t end_r = min(own_r, lv.H), end_c = min(own_c, lv.W);
-        const uint32_t spr = (uint32_t)lv.items_per_row;
-        const uint32_t per_plane = (uint32_t)lv.rows * spr;
-        const uint32_t items = (uint32_t)nplanes * per_plane;
-        const bool vec_store_ok = (lv.W & 3) == 0 && ((k.TW & 3) == 0 || k.tiles_w == 1);
-        const int32_t spec = (p.kw == 3 && p.sw == 2) ? 1 : (p.kw == 3 && p.sw == 1) ? 2 : (p.kw == 2 && p.sw == 2) ? 3 : 0;
-        for (uint32_t i = tid; i < items; i += nthr) {
-            const uint32_t pl = fdiv(i, lv.div_plane);
-            const uint32_t rem = i - pl * per_plane;
-            const uint32_t r = fdiv(rem, lv.div_row);
-            const uint32_t j = rem - r * spr;
-            const uint32_t plane = (uint32_t)plane0 + pl;
-            const int32_t gr = r0 + (int32_t)r, gc = c0 + 4 * (int32_t)j;
-            const int32_t h0 = gr * p.sh - p.ph, w0 = gc * p.sw - p.pw;
-            const float *sp = src + pl * (uint32_t)pv.plane_stride + (r * (uint32_t)p.sh) * (uint32_t)pv.pitch + 4u * j * (uint32_t)p.sw;
-            float val[4];
-            int32_t bi[4] = {0, 0, 0, 0};
-            if (idxp) {
-                if (spec == 1) pool_strip<3, 2, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-                else if (spec == 2) pool_strip<3, 1, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-                else if (spec == 3) pool_strip<2, 2, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-                else pool_strip<0, 0, true>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-            } else {
-                if (spec == 1) pool_strip<3, 2, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-                else if (spec == 2) pool_strip<3, 1, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-                else if (spec == 3) pool_strip<2, 2, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-                else pool_strip<0, 0, false>(p, sp, pv.pitch, h0, w0, pv.H, pv.W, val, bi);
-            }
-            if (p.kind != OP_MAXPOOL) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) val[e] = round_store<BF16>(val[e]);
-            }
-            const bool row_in = gr >= 0 && gr < lv.H;
-            // global offset of the strip at this level (clamped to a safe address off-plane)
-            const bool strip_in = row_in && gc >= 0 && gc + 3 < lv.W;
-            const uint32_t goff = (plane * (uint32_t)lv.H + (uint32_t)(row_in ? gr : 0)) * (uint32_t)lv.W;
-            if (idxp && row_in && gr < end_r) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (gc + e >= 0 && gc + e < end_c) idxp[goff + (uint32_t)(gc + e)] = bi[e];
-            }
-            // element-wise operations attached to this level
-            if (lv.n_ew > 0) {
-                float x[4][1] = {{val[0]}, {val[1]}, {val[2]}, {val[3]}};
-                int32_t c1[4];
-                uint32_t o1[4];
-                const int32_t ch = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    c1[e] = ch;
-                    const int32_t cc = gc + e;
-                    o1[e] = (row_in && cc >= 0 && cc < lv.W) ? goff + (uint32_t)cc : 0u;
-                }
-                apply_ew<BF16, 1, 4>(x, c1, o1, lv.ew, lv.n_ew, k.params, k.C, k.res);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) val[e] = x[e][0];
-            }
-            if (last) {
-                if (row_in && gr < end_r) {
-                    if (strip_in && gc + 3 < end_c && vec_store_ok) {
-                        store_elems<BF16, 4>(k.out, goff + (uint32_t)gc, val);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (gc + e >= 0 && gc + e < end_c) {
-                                const float one[1] = {val[e]};
-                                store_elems<BF16, 1>(k.out, goff + (uint32_t)(gc + e), one);
-                            }
-                    }
-                }
-            } else {
-                float4 w;
-                w.x = (row_in && gc >= 0 && gc < lv.W) ? val[0] : padv;
-                w.y = (row_in && gc + 1 >= 0 && gc + 1 < lv.W) ? val[1] : padv;
-                w.z = (row_in && gc + 2 >= 0 && gc + 2 < lv.W) ? val[2] : padv;
-                w.w = (row_in && gc + 3 >= 0 && gc + 3 < lv.W) ? val[3] : padv;
-                *reinterpret_cast<float4 *>(dst + pl * (uint32_t)lv.plane_stride + r * (uint32_t)lv.pitch + 4u * j) = w;
-            }
+        // tile's rectangle starts, so every cell is written exactly once
+        const int32_t own_r = (ti + 1 < k.tiles_h) ? cx.r0 + step_r : lv.H;
+        const int32_t own_c = (tj + 1 < k.tiles_w) ? cx.c0 + step_c : lv.W;
+        cx.end_r = min(own_r, lv.H);
+        cx.end_c = min(own_c, lv.W);
+        cx.d_lo = (l == 1) ? k.delta0 : 0;
+        cx.nplanes = nplanes;
+        cx.plane0 = plane0;
+        cx.vec_store_ok = cx.last && (lv.W & 3) == 0 && ((k.TW & 3) == 0 || k.tiles_w == 1);
+        const int32_t d = cx.d_lo & 3;
+        if (cx.idxp) {
+            if (d == 0) pool_phase_dispatch<BF16, 0, true>(k, lv, pv, p, cx);
+            else if (d == 1) pool_phase_dispatch<BF16, 1, true>(k, lv, pv, p, cx);
+            else if (d == 2) pool_phase_dispatch<BF16, 2, true>(k, lv, pv, p, cx);
+            else pool_phase_dispatch<BF16, 3, true>(k, lv, pv, p, cx);
+        } else {
+            if (d == 0) pool_phase_dispatch<BF16, 0, false>(k, lv, pv, p, cx);
+            else if (d == 1) pool_phase_dispatch<BF16, 1, false>(k, lv, pv, p, cx);
+            else if (d == 2) pool_phase_dispatch<BF16, 2, false>(k, lv, pv, p, cx);
+            else pool_phase_dispatch<BF16, 3, false>(k, lv, pv, p, cx);
         }
-        if (!last) __syncthreads();
+        if (!cx.last) __syncthreads();
     }
 }
 

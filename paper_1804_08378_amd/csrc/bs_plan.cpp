@@ -144,6 +144,7 @@ struct LdsGeom {
     std::vector<int32_t> H, W;        // index 0..L
     std::vector<int32_t> rows, cols;  // region extents per level
     std::vector<int32_t> pitch;
+    int32_t delta0 = 0, nvr = 0;      // level-0 LDS row: starts delta0 columns before the rectangle, nvr vectors
     uint64_t lds_bytes = 0;
     uint64_t buf_floats[2] = {0, 0};
     double redundancy = 1.0;
@@ -151,9 +152,10 @@ struct LdsGeom {
 
 static inline int32_t round4(int32_t v) { return (v + 3) / 4 * 4; }
 
-// in-plane cells of [origin, origin + extent) summed over all tiles, along one dimension
+// in-plane cells of [origin - before, origin - before + extent) summed over all tiles, along
+// one dimension
 static uint64_t loaded_extent(const std::vector<Dim> &d, const std::vector<int32_t> &size, int32_t tile,
-                              int32_t extent0, int32_t vec0)
+                              int32_t before, int32_t extent)
 {
     const int L = (int)d.size() - 1;
     const int32_t n_tiles = (size[L] + tile - 1) / tile;
@@ -161,11 +163,8 @@ static uint64_t loaded_extent(const std::vector<Dim> &d, const std::vector<int32
     for (int32_t t = 0; t < n_tiles; ++t) {
         int64_t o = (int64_t)t * tile;
         for (int l = L; l >= 1; --l) o = o * d[l].s - d[l].p;
-        int64_t lo = std::max<int64_t>(o, 0), hi = std::min<int64_t>(o + extent0, size[0]);
-        if (vec0 > 1) {
-            lo = lo / vec0 * vec0;
-            hi = (hi + vec0 - 1) / vec0 * vec0;
-        }
+        o -= before;
+        const int64_t lo = std::max<int64_t>(o, 0), hi = std::min<int64_t>(o + extent, size[0]);
         if (hi > lo) sum += (uint64_t)(hi - lo);
     }
     return sum;
@@ -197,16 +196,22 @@ static void lds_geometry(const bs_stack *s, int32_t first_op, int32_t n_ops, int
         g.cols[l - 1] = (g.cols[l] - 1) * g.dw[l].s + g.dw[l].k;
         if (l - 1 >= 1) g.cols[l - 1] = round4(g.cols[l - 1]);
     }
+    // level-0 LDS rows start at the 128-bit global vector holding the rectangle's first column
+    int64_t c00 = 0;
+    for (int l = L; l >= 1; --l) c00 = c00 * g.dw[l].s - g.dw[l].p;
+    g.delta0 = vec0 > 1 ? (int32_t)(((c00 % vec0) + vec0) % vec0) : 0;
+    g.nvr = vec0 > 1 ? (g.delta0 + g.cols[0] + vec0 - 1) / vec0 : g.cols[0];
     g.buf_floats[0] = g.buf_floats[1] = 0;
     for (int l = 0; l <= L; ++l) {
         g.pitch[l] = round4(g.cols[l]);
+        if (l == 0 && vec0 > 1) g.pitch[0] = g.nvr * vec0 + 4;  // + slack for aligned over-reads
         if (l == L) continue;  // level L goes to memory, not to LDS
         const uint64_t need = (uint64_t)ppg * g.rows[l] * g.pitch[l];
         g.buf_floats[l & 1] = std::max(g.buf_floats[l & 1], need);
     }
     g.lds_bytes = (g.buf_floats[0] + g.buf_floats[1]) * sizeof(float);
-    const uint64_t rsum = loaded_extent(g.dh, g.H, th, g.rows[0], 1);
-    const uint64_t csum = loaded_extent(g.dw, g.W, tw, g.cols[0], vec0);
+    const uint64_t rsum = loaded_extent(g.dh, g.H, th, 0, g.rows[0]);
+    const uint64_t csum = loaded_extent(g.dw, g.W, tw, g.delta0, vec0 > 1 ? g.nvr * vec0 : g.cols[0]);
     g.redundancy = (double)rsum * (double)csum / ((double)g.H[0] * (double)g.W[0]);
 }
 
@@ -425,9 +430,17 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
     int32_t best_th = 0, best_tw = 0, best_ppg = 0;
     double best_score = 1e300;
     LdsGeom g;
+    int32_t sprod_w0 = 1;
+    for (int32_t i = q.first_op; i < q.first_op + q.n_ops; ++i)
+        if (!op_is_elementwise(s->ops[i].kind)) sprod_w0 *= s->ops[i].sw;
+    // the level-0 LDS rows of all tiles must start at the same offset inside a 128-bit vector
+    auto vec_for = [&](int32_t tw) {
+        const int64_t ntw = (WL + tw - 1) / tw;
+        return (ntw == 1 || ((int64_t)tw * sprod_w0) % vec0 == 0) ? vec0 : 1;
+    };
     auto consider = [&](int32_t th, int32_t tw, int32_t ppg) {
         if (th < 1 || tw < 1 || ppg < 1 || th > HL || tw > WL || ppg > planes) return;
-        lds_geometry(s, q.first_op, q.n_ops, th, tw, ppg, vec0, g);
+        lds_geometry(s, q.first_op, q.n_ops, th, tw, ppg, vec_for(tw), g);
         if (g.lds_bytes > budget) return;
         const int64_t nth = (HL + th - 1) / th, ntw = (WL + tw - 1) / tw;
         const int64_t grid = nth * ntw * ((planes + ppg - 1) / ppg);
@@ -447,6 +460,7 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
         if ((double)grid < want) score *= 1.0 + 0.25 * (want - grid) / want;
         score *= 1.0 + 0.25 * (double)g.lds_bytes / (double)std::max<uint64_t>(budget, 1);
         if (tw != WL) score *= 1.05;
+        if (vec_for(tw) != vec0) score *= 1.5;
         if (score < best_score) {
             best_score = score;
             best_th = th; best_tw = tw; best_ppg = ppg;
@@ -471,11 +485,12 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
     }
     if (best_th == 0) return BS_ERR_NO_FIT;
 
-    lds_geometry(s, q.first_op, q.n_ops, best_th, best_tw, best_ppg, vec0, g);
+    const int32_t vec_eff = vec_for(best_tw);
+    lds_geometry(s, q.first_op, q.n_ops, best_th, best_tw, best_ppg, vec_eff, g);
     q.tile_rows = best_th;
     q.tile_cols = best_tw;
     q.planes_per_group = best_ppg;
-    q.vec = vec0;
+    q.vec = vec_eff;
     q.lds_bytes = g.lds_bytes;
     q.redundancy = g.redundancy;
     q.n_levels = g.L;
@@ -493,7 +508,8 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
     k.tiles_h = (HL + best_th - 1) / best_th;
     k.tiles_w = (WL + best_tw - 1) / best_tw;
     k.PPG = best_ppg;
-    k.vec = vec0;
+    k.vec = vec_eff;
+    k.delta0 = g.delta0;
     k.div_tiles_w = make_fastdiv((uint32_t)k.tiles_w);
     k.div_tiles_hw = make_fastdiv((uint32_t)(k.tiles_w * k.tiles_h));
     k.div_c = make_fastdiv((uint32_t)k.C);
@@ -508,9 +524,10 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
         lv.plane_stride = lv.rows * lv.pitch;
         lv.buf_off = (l & 1) ? (int32_t)g.buf_floats[0] : 0;
         lv.n_ew = 0;
-        lv.items_per_row = (l == 0) ? (vec0 > 1 ? (lv.cols + vec0 - 1) / vec0 + 1 : lv.cols) : lv.cols / 4;
-        lv.div_row = make_fastdiv((uint32_t)lv.items_per_row);
-        lv.div_plane = make_fastdiv((uint32_t)(lv.rows * lv.items_per_row));
+        lv.items_per_row = (l == 0) ? g.nvr : lv.cols / 4;
+        lv.ct = std::min(lv.items_per_row, q.threads);
+        lv.rt = q.threads / lv.ct;
+        lv.div_ct = make_fastdiv((uint32_t)lv.ct);
     }
     for (int32_t i = q.first_op; i < q.first_op + q.n_ops; ++i) {
         const Op &op = s->ops[i];
@@ -567,8 +584,25 @@ static bool audit_lds(const Sequence &q)
         if (l + 1 < L && (l & 1) == ((l + 1) & 1)) return false;
     }
     const LevelK &l0 = k.level[0];
-    const int32_t want0 = k.vec > 1 ? (l0.cols + k.vec - 1) / k.vec + 1 : l0.cols;
-    if (l0.items_per_row != want0) return false;
+    if (k.vec > 1) {
+        // all tiles share delta0; the vectors of a row cover the rectangle; aligned over-reads of
+        // up to 3 floats stay inside the row pitch
+        if (k.delta0 != (int32_t)(((lo_c % k.vec) + k.vec) % k.vec)) return false;
+        if (k.tiles_w > 1) {
+            int64_t step_c = k.TW;
+            for (int m = L; m >= 1; --m) step_c *= k.pool[m].sw;
+            if (step_c % k.vec) return false;
+        }
+        if (l0.items_per_row * k.vec < k.delta0 + l0.cols) return false;
+        if (l0.pitch < l0.items_per_row * k.vec + 4) return false;
+    } else {
+        if (k.delta0 != 0 || l0.items_per_row != l0.cols) return false;
+    }
+    for (int l = 0; l <= L; ++l) {
+        const LevelK &lv = k.level[l];
+        if (lv.ct < 1 || lv.rt < 1 || lv.ct * lv.rt > q.threads || lv.ct > lv.items_per_row) return false;
+        if (lv.div_ct.d != (uint32_t)lv.ct) return false;
+    }
     return true;
 }
 
