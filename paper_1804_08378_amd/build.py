@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbrainslug_hip.so")
-SOURCES = ["bs_stack.cpp", "bs_plan.cpp", "bs_run.cpp", "bs_kernels.hip"]
+SOURCES = ["bs_stack.cpp", "bs_plan.cpp", "bs_run.cpp", "bs_kernels.hip", "bs_lds.hip"]
 
 # -ffp-contract=off: the only fused multiply-add is the explicit one of BatchNorm.
 # packed-fp32 instructions are disabled for the device code.
@@ -29,7 +29,7 @@ def up_to_date() -> bool:
     if not os.path.exists(LIB):
         return False
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "bs_internal.h"), os.path.join(ROOT, "include", "brainslug.h")]
+    deps = sources() + [os.path.join(CSRC, "bs_internal.h"), os.path.join(CSRC, "bs_device.h"), os.path.join(ROOT, "include", "brainslug.h")]
     return all(os.path.getmtime(d) <= t for d in deps)
 
 
@@ -37,11 +37,24 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and up_to_date():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+
+    def compile_one(src):
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        cmd = [hipcc, *compile_flags, "-x", "hip", "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True)
+        return obj
+
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        objs = list(ex.map(compile_one, sources()))
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc, *FLAGS, "-x", "hip", *sources(), "-o", tmp]
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", *objs, "-o", tmp],
+                   check=True)
     os.replace(tmp, LIB)
     return LIB
 

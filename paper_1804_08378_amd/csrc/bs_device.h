@@ -1,0 +1,125 @@
+// Device-side helpers shared by the HIP kernels: fast division, bfloat16 conversion,
+// 128-bit register blocks and their loads / stores.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "bs_internal.h"
+
+namespace bs {
+
+
+#define BS_DEV __device__ __forceinline__
+
+BS_DEV uint32_t fdiv(uint32_t n, const FastDiv &f)
+{
+    return f.d == 1 ? n : (__umulhi(n, f.mul) >> f.shift);
+}
+
+// ------------------------------------------------------------------ bfloat16
+BS_DEV float bf16_round(float f)
+{
+    // round-to-nearest-even through the compiler's bfloat16 type (v_cvt_pk_bf16_f32)
+    return (float)(__bf16)f;
+}
+BS_DEV uint16_t bf16_bits(float f)
+{
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, h);
+}
+BS_DEV float bf16_up(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+template <bool BF16>
+BS_DEV float round_store(float v)
+{
+    if constexpr (BF16) return bf16_round(v);
+    else return v;
+}
+
+// --------------------------------------------------------- vector load/store
+// Raw register block of N consecutive elements (2, 4, 8 or 16 bytes, one load instruction).
+template <int BYTES>
+struct RawT;
+template <>
+struct RawT<16> { using type = uint4; };
+template <>
+struct RawT<8> { using type = uint2; };
+template <>
+struct RawT<4> { using type = uint32_t; };
+template <>
+struct RawT<2> { using type = uint16_t; };
+
+template <bool BF16, int N>
+struct Raw {
+    using type = typename RawT<N * (BF16 ? 2 : 4)>::type;
+    type q;
+};
+
+template <bool BF16, int N>
+BS_DEV Raw<BF16, N> load_raw(const void *base, uint32_t elem)
+{
+    using T = typename Raw<BF16, N>::type;
+    Raw<BF16, N> r;
+    r.q = *reinterpret_cast<const T *>(static_cast<const char *>(base) + (size_t)elem * (BF16 ? 2 : 4));
+    return r;
+}
+
+template <bool BF16, int N>
+BS_DEV void unpack(const Raw<BF16, N> &r, float (&v)[N])
+{
+    constexpr int BYTES = N * (BF16 ? 2 : 4);
+    if constexpr (BYTES == 2) {
+        v[0] = __uint_as_float((uint32_t)r.q << 16);
+    } else {
+        constexpr int WORDS = BYTES / 4;
+        uint32_t w[WORDS];
+        if constexpr (BYTES == 16) { w[0] = r.q.x; w[1] = r.q.y; w[2] = r.q.z; w[3] = r.q.w; }
+        else if constexpr (BYTES == 8) { w[0] = r.q.x; w[1] = r.q.y; }
+        else w[0] = r.q;
+        if constexpr (!BF16) {
+#pragma unroll
+            for (int i = 0; i < WORDS; ++i) v[i] = __uint_as_float(w[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < WORDS; ++i) {
+                v[2 * i] = __uint_as_float(w[i] << 16);
+                v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            }
+        }
+    }
+}
+
+// Store N consecutive elements (N * element size is 2, 4, 8 or 16 bytes, naturally aligned).
+template <bool BF16, int N>
+BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
+{
+    if constexpr (!BF16) {
+        float *p = static_cast<float *>(base) + elem;
+        if constexpr (N == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        else if constexpr (N == 2) *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+        else {
+#pragma unroll
+            for (int i = 0; i < N; ++i) p[i] = v[i];
+        }
+    } else {
+        uint16_t *p = static_cast<uint16_t *>(base) + elem;
+        if constexpr (N == 8 || N == 4 || N == 2) {
+            uint32_t w[N / 2];
+#pragma unroll
+            for (int i = 0; i < N / 2; ++i)
+                w[i] = (uint32_t)bf16_bits(v[2 * i]) | ((uint32_t)bf16_bits(v[2 * i + 1]) << 16);
+            if constexpr (N == 8) *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+            else if constexpr (N == 4) *reinterpret_cast<uint2 *>(p) = make_uint2(w[0], w[1]);
+            else *reinterpret_cast<uint32_t *>(p) = w[0];
+        } else {
+#pragma unroll
+            for (int i = 0; i < N; ++i) p[i] = bf16_bits(v[i]);
+        }
+    }
+}
+
+
+}  // namespace bs

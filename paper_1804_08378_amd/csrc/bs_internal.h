@@ -230,5 +230,7 @@ void free_params(bs_stack *s);
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
                           const void *const *res, int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
+// bs_lds.hip
+bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
 
 }  // namespace bs
