@@ -82,7 +82,8 @@ struct LevelK {
     int32_t buf_off;         // float offset of this level's buffer in dynamic LDS
     int32_t n_ew;
     EwOp ew[K_MAX_EW];       // applied to a value once it exists at this level
-    int32_t items_per_row;   // level 0: global vectors per region row; else strips of 4 outputs
+    int32_t vo;              // outputs one lane produces per strip at this level (levels >= 1)
+    int32_t items_per_row;   // level 0: global vectors per region row; else strips of vo outputs
     int32_t ct, rt;          // lane grid of a phase: ct = min(items_per_row, threads) lanes along a
                              // row, rt = threads / ct rows in flight
     FastDiv div_ct;          // by ct
@@ -145,6 +146,18 @@ struct Origins {
 #else
 #define BS_HD inline
 #endif
+
+// Outputs one lane produces per strip of a pooling phase, by column stride.  Two per lane for
+// stride 2 would make consecutive lanes read LDS four floats apart (no bank conflicts), but it
+// doubles the per-output address and predicate work; measured on MI355X four per lane is faster
+// for every BASELINE stack, so the rule is constant.  Planner, audit and kernels all use it.
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+constexpr int32_t strip_outputs(int32_t sw)
+{
+    return sw >= 1 ? 4 : 4;
+}
 
 BS_HD void origin_step(const PoolK &p, int32_t &r0, int32_t &c0)
 {

@@ -175,25 +175,35 @@ BS_DEV void lds_read_row(const float *p, float (&r)[N])
     if constexpr (R == 3) r[4 * Q + 2] = p[4 * Q + 2];
 }
 
-// One strip of four outputs of pooling operation P from the cached level below.
+template <class P>
+struct StripVO {
+    static constexpr int value = 4;  // run-time shapes: register room for the widest strip
+};
+template <int KIND, int KH, int KW, int SH, int SW, int PH, int PW, int CIP>
+struct StripVO<PoolSpec<KIND, KH, KW, SH, SW, PH, PW, CIP>> {
+    static constexpr int value = strip_outputs(SW);
+};
+
+// One strip of VO outputs of pooling operation P from the cached level below.
 //   src      16-byte aligned LDS address; the strip's first window starts D (static shapes)
 //            or d_rt (run-time shapes) floats after it
 //   h0, w0   global row / column of the first window's first cell in the input plane (may be
 //            negative: padding)
-template <class P, int D, bool WANT_IDX>
-BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t pitch, int32_t h0, int32_t w0,
-                       int32_t Hp, int32_t Wp, float (&val)[4], int32_t (&bidx)[4])
+//   vo       outputs actually wanted (run-time shapes; static shapes produce all VO)
+template <class P, int VO, int D, bool WANT_IDX>
+BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t vo, int32_t pitch, int32_t h0,
+                       int32_t w0, int32_t Hp, int32_t Wp, float (&val)[VO], int32_t (&bidx)[VO])
 {
     const bool is_max = p.kind() == OP_MAXPOOL;
-    float acc[4];
+    float acc[VO];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < VO; ++e) {
         acc[e] = is_max ? -INFINITY : 0.0f;
         if constexpr (WANT_IDX) bidx[e] = max(h0, 0) * Wp + max(w0 + e * p.sw(), 0);  // first in-range cell
     }
     if constexpr (P::is_static) {
         constexpr int KH = P::kh(), KW = P::kw(), SW = P::sw();
-        constexpr int NC = 3 * SW + KW;                           // columns four windows span
+        constexpr int NC = (VO - 1) * SW + KW;                    // columns the windows span
         constexpr int NR = D == 0 ? NC : (D + NC + 3) / 4 * 4;    // floats read per row
         float r[KH][NR];
 #pragma unroll
@@ -202,7 +212,7 @@ BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t pitch
 #pragma unroll
             for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+                for (int e = 0; e < VO; ++e)
 #pragma unroll
                     for (int dw = 0; dw < KW; ++dw) {
                         const float v = r[dh][D + e * SW + dw];
@@ -218,7 +228,7 @@ BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t pitch
 #pragma unroll
             for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+                for (int e = 0; e < VO; ++e)
 #pragma unroll
                     for (int dw = 0; dw < KW; ++dw) acc[e] = acc[e] + r[dh][D + e * SW + dw];
         }
@@ -228,7 +238,8 @@ BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t pitch
             const float *rowp = src + dh * pitch + d_rt;
             const int32_t rbase = (h0 + dh) * Wp + w0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
+            for (int e = 0; e < VO; ++e) {
+                if (e >= vo) break;
                 for (int32_t dw = 0; dw < kw; ++dw) {
                     const float v = rowp[e * sw + dw];
                     if (is_max) {
@@ -239,18 +250,19 @@ BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t pitch
                         acc[e] = acc[e] + v;
                     }
                 }
+            }
         }
     }
     if (is_max) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) val[e] = acc[e];
+        for (int e = 0; e < VO; ++e) val[e] = acc[e];
     } else if (p.cip()) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) val[e] = acc[e] * p.inv_kk();
+        for (int e = 0; e < VO; ++e) val[e] = acc[e] * p.inv_kk();
     } else {
         const int32_t nr = min(h0 + p.kh(), Hp) - max(h0, 0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < VO; ++e) {
             const int32_t we = w0 + e * p.sw();
             const int32_t nc = min(we + p.kw(), Wp) - max(we, 0);
             // windows wholly outside the plane can make nr * nc <= 0; such outputs are never stored
@@ -356,6 +368,8 @@ template <bool BF16, class P, class EW, int D, bool WANT_IDX, bool LAST>
 BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, const LevelK &pv, const P &p,
                        const PhaseCtx &cx)
 {
+    constexpr int VO = StripVO<P>::value;
+    const int32_t vo = P::is_static ? VO : lv.vo;
     const uint32_t tid = threadIdx.x;
     const uint32_t ty = fdiv(tid, lv.div_ct), tx = tid - ty * (uint32_t)lv.ct;
     if ((int32_t)ty >= lv.rt) return;
@@ -369,62 +383,71 @@ BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, con
         float *dplane = cx.dst + pl * lv.plane_stride;
         const uint32_t gplane = plane * (uint32_t)(lv.H * lv.W);
         for (int32_t j = (int32_t)tx; j < spr; j += lv.ct) {
-            const int32_t gc = cx.c0 + 4 * j;
+            const int32_t gc = cx.c0 + vo * j;
             const int32_t w0 = gc * p.sw() - p.pw();
             // aligned LDS column where this strip's reads start; its first window starts D (or,
             // for run-time shapes, d_rt) floats later
-            const int32_t scol = 4 * j * p.sw() + (P::is_static ? (cx.d_lo - D) : 0);
+            const int32_t scol = vo * j * p.sw() + (P::is_static ? (cx.d_lo - D) : 0);
             const int32_t d_rt = P::is_static ? 0 : cx.d_lo;
-            bool cin[4];
+            bool cin[VO];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) cin[e] = gc + e >= 0 && gc + e < lv.W;
-            const bool strip_vec = cx.vec_store_ok && gc >= 0 && gc + 3 < cx.end_c;
+            for (int e = 0; e < VO; ++e) cin[e] = e < vo && gc + e >= 0 && gc + e < lv.W;
+            const bool strip_vec = P::is_static && cx.vec_store_ok && gc >= 0 && gc + VO - 1 < cx.end_c;
             for (int32_t r = (int32_t)ty; r < lv.rows; r += lv.rt) {
                 const int32_t gr = cx.r0 + r;
                 const int32_t h0 = gr * p.sh() - p.ph();
-                float val[4];
-                int32_t bi[4] = {0, 0, 0, 0};
-                pool_strip<P, D, WANT_IDX>(p, splane + (r * p.sh()) * pv.pitch + scol, d_rt, pv.pitch, h0, w0,
-                                           pv.H, pv.W, val, bi);
+                float val[VO];
+                int32_t bi[VO];
+#pragma unroll
+                for (int e = 0; e < VO; ++e) bi[e] = 0;
+                pool_strip<P, VO, D, WANT_IDX>(p, splane + (r * p.sh()) * pv.pitch + scol, d_rt, vo, pv.pitch, h0,
+                                               w0, pv.H, pv.W, val, bi);
                 if (p.kind() != OP_MAXPOOL) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) val[e] = round_store<BF16>(val[e]);
+                    for (int e = 0; e < VO; ++e) val[e] = round_store<BF16>(val[e]);
                 }
                 const bool row_in = gr >= 0 && gr < lv.H;
                 const uint32_t goff = gplane + (uint32_t)(row_in ? gr : 0) * (uint32_t)lv.W;
                 if constexpr (WANT_IDX) {
                     if (cx.idxp && row_in && gr < cx.end_r) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (gc + e >= 0 && gc + e < cx.end_c) cx.idxp[goff + (uint32_t)(gc + e)] = bi[e];
+                        for (int e = 0; e < VO; ++e)
+                            if (cin[e] && gc + e < cx.end_c) cx.idxp[goff + (uint32_t)(gc + e)] = bi[e];
                     }
                 }
                 if (EW::count(lv) > 0) {
-                    uint32_t o4[4];
+                    uint32_t o4[VO];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o4[e] = (row_in && cin[e]) ? goff + (uint32_t)(gc + e) : 0u;
-                    apply_level_ew<BF16, 4, false, EW>(val, lv, er, k.res, o4);
+                    for (int e = 0; e < VO; ++e) o4[e] = (row_in && cin[e]) ? goff + (uint32_t)(gc + e) : 0u;
+                    apply_level_ew<BF16, VO, false, EW>(val, lv, er, k.res, o4);
                 }
                 if (LAST) {
                     if (row_in && gr < cx.end_r) {
                         if (strip_vec) {
-                            store_elems<BF16, 4>(k.out, goff + (uint32_t)gc, val);
+                            store_elems<BF16, VO>(k.out, goff + (uint32_t)gc, val);
                         } else {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (gc + e >= 0 && gc + e < cx.end_c) {
+                            for (int e = 0; e < VO; ++e)
+                                if (cin[e] && gc + e < cx.end_c) {
                                     const float one[1] = {val[e]};
                                     store_elems<BF16, 1>(k.out, goff + (uint32_t)(gc + e), one);
                                 }
                         }
                     }
                 } else {
-                    float4 w;
-                    w.x = (row_in && cin[0]) ? val[0] : cx.padv;
-                    w.y = (row_in && cin[1]) ? val[1] : cx.padv;
-                    w.z = (row_in && cin[2]) ? val[2] : cx.padv;
-                    w.w = (row_in && cin[3]) ? val[3] : cx.padv;
-                    *reinterpret_cast<float4 *>(dplane + r * lv.pitch + 4 * j) = w;
+                    float w[VO];
+#pragma unroll
+                    for (int e = 0; e < VO; ++e) w[e] = (row_in && cin[e]) ? val[e] : cx.padv;
+                    float *d = dplane + r * lv.pitch + vo * j;
+                    if constexpr (P::is_static && VO == 4) {
+                        *reinterpret_cast<float4 *>(d) = make_float4(w[0], w[1], w[2], w[3]);
+                    } else if constexpr (P::is_static && VO == 2) {
+                        *reinterpret_cast<float2 *>(d) = make_float2(w[0], w[1]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < VO; ++e)
+                            if (e < vo) d[e] = w[e];
+                    }
                 }
             }
         }
@@ -458,7 +481,7 @@ BS_DEV PhaseCtx phase_ctx(const LdsSeqK &k, const TileCtx &t, float *lds, int32_
     cx.end_r = min(own_r, lv.H);
     cx.end_c = min(own_c, lv.W);
     cx.d_lo = (l == 1) ? k.delta0 : 0;
-    cx.vec_store_ok = cx.last && (lv.W & 3) == 0 && ((k.TW & 3) == 0 || k.tiles_w == 1);
+    cx.vec_store_ok = cx.last && (lv.W % lv.vo) == 0 && ((k.TW % lv.vo) == 0 || k.tiles_w == 1);
     return cx;
 }
 

@@ -451,7 +451,8 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
         score *= (double)(nth * th) / HL * (double)(ntw * tw) / WL;
         double worst_fill = 1.0;
         for (int l = 1; l <= g.L; ++l) {
-            const double strips = (double)ppg * g.rows[l] * (g.cols[l] / 4);
+            const int32_t vo = strip_outputs(g.dw[l].s);
+            const double strips = (double)g.rows[l] * (g.cols[l] / vo);
             const double passes = std::ceil(strips / q.threads);
             worst_fill = std::min(worst_fill, strips / (passes * q.threads));
         }
@@ -524,7 +525,8 @@ static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options 
         lv.plane_stride = lv.rows * lv.pitch;
         lv.buf_off = (l & 1) ? (int32_t)g.buf_floats[0] : 0;
         lv.n_ew = 0;
-        lv.items_per_row = (l == 0) ? g.nvr : lv.cols / 4;
+        lv.vo = (l == 0) ? 1 : strip_outputs(g.dw[l].s);
+        lv.items_per_row = (l == 0) ? g.nvr : lv.cols / lv.vo;
         lv.ct = std::min(lv.items_per_row, q.threads);
         lv.rt = q.threads / lv.ct;
         lv.div_ct = make_fastdiv((uint32_t)lv.ct);
@@ -562,7 +564,8 @@ static bool audit_lds(const Sequence &q)
         const LevelK &lv = k.level[l], &pv = k.level[l - 1];
         const PoolK &p = k.pool[l];
         if (p.kh < 1 || p.kw < 1 || p.sh < 1 || p.sw < 1) return false;
-        if (lv.cols % 4 || lv.items_per_row != lv.cols / 4) return false;
+        if (lv.vo != strip_outputs(p.sw)) return false;
+        if (lv.cols % 4 || lv.items_per_row != lv.cols / lv.vo) return false;
         if (pv.rows < (lv.rows - 1) * p.sh + p.kh) return false;
         if (pv.cols < (lv.cols - 1) * p.sw + p.kw) return false;
         lo_r = lo_r * p.sh - p.ph;

@@ -1,0 +1,140 @@
+"""Host-only checks of the C-ABI library (no GPU, no compute calls): it loads, exports
+every symbol include/brainslug.h declares, validates its arguments, folds BatchNorm
+as the header says, and reports shapes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1804_08378_amd import brainslug as bs
+from paper_1804_08378_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "brainslug.h")).read()
+    declared = set(re.findall(r"BS_API\s+[\w\s\*]+?\b(bs_\w+)\s*\(", hdr))
+    assert declared, "no BS_API declarations found"
+    lib = C.CDLL(bs.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in brainslug.h but not exported"
+    assert declared == set(bs.EXPORTS), declared ^ set(bs.EXPORTS)
+    assert bs.bs_version().startswith("brainslug-hip")
+    assert bs.bs_status_string(0) == "ok" and bs.bs_status_string(6)
+
+
+def _status(fn, *a, **k):
+    with pytest.raises(bs.BrainSlugError) as e:
+        fn(*a, **k)
+    return e.value.status
+
+
+def test_create_rejects_bad_arguments():
+    ok_bn = wl.bn_params(4, 0)
+    assert _status(bs.bs_stack_create, [wl.relu()], (0, 4, 8, 8), "f32") == 2      # shape
+    assert _status(bs.bs_stack_create, [wl.relu()], (1, 4, 8, -1), "f32") == 2
+    assert _status(bs.bs_stack_create, [], (1, 4, 8, 8), "f32") == 4                # no layers
+    assert _status(bs.bs_stack_create, [wl.relu()] * 257, (1, 4, 8, 8), "f32") == 4
+    assert _status(bs.bs_stack_create, [wl.relu()], (1, 4, 8, 8), 7) == 4            # dtype
+    assert _status(bs.bs_stack_create, [wl.maxpool(3, 1, 0)], (1, 4, 2, 2), "f32") == 2  # empty output
+    assert _status(bs.bs_stack_create, [wl.maxpool(2, 2, 2)], (1, 4, 8, 8), "f32") == 3  # p > k/2
+    assert _status(bs.bs_stack_create, [wl.maxpool(0, 1, 0)], (1, 4, 8, 8), "f32") == 3
+    assert _status(bs.bs_stack_create, [wl.avgpool(2, 0, 0)], (1, 4, 8, 8), "f32") == 3
+    ceil = dict(wl.maxpool(2, 2), ceil_mode=True)
+    assert _status(bs.bs_stack_create, [ceil], (1, 4, 8, 8), "f32") == 4
+    dil = dict(wl.maxpool(2, 2), dilation=(2, 2))
+    assert _status(bs.bs_stack_create, [dil], (1, 4, 8, 8), "f32") == 4
+    bad = dict(ok_bn, var=np.array([1, 1, -1, 1], np.float32))
+    assert _status(bs.bs_stack_create, [bad], (1, 4, 8, 8), "f32") == 3             # var + eps <= 0
+    nan = dict(ok_bn, gamma=np.array([1, np.nan, 1, 1], np.float32))
+    assert _status(bs.bs_stack_create, [nan], (1, 4, 8, 8), "f32") == 3
+    assert _status(bs.bs_stack_create, [wl.add()] * 17, (1, 4, 8, 8), "f32") == 4
+    too_big = (4, 1024, 1024, 1024)
+    assert _status(bs.bs_stack_create, [wl.relu()], too_big, "f32") == 4
+    # NULL handling straight at the ABI
+    lib = bs.load()
+    h = C.c_void_p()
+    shape = (C.c_int64 * 4)(1, 4, 8, 8)
+    assert lib.bs_stack_create(None, 1, shape, 0, C.byref(h)) == 1
+    d = (bs.bs_layer_desc * 1)()
+    d[0].kind = bs.BS_BATCHNORM  # parameter pointers left NULL
+    assert lib.bs_stack_create(d, 1, shape, 0, C.byref(h)) == 1
+    lib.bs_stack_destroy(None)  # allowed
+    assert lib.bs_stack_num_residuals(None) == -1 and lib.bs_stack_num_index_outputs(None) == -1
+    assert lib.bs_stack_output_shape(None, shape) == 1
+
+
+def test_shapes_residuals_indices():
+    layers = [wl.bn_params(6, 1), wl.add(), wl.maxpool(3, 2, 1, True), wl.relu(), wl.add(),
+              wl.avgpool((2, 3), (2, 1), (1, 1)), wl.maxpool(2, 1, 0, True)]
+    shape = (2, 6, 17, 23)
+    h = bs.bs_stack_create(layers, shape, "bf16")
+    try:
+        assert bs.bs_stack_output_shape(h) == wl.output_shape(layers, shape) == (2, 6, 4, 11)
+        assert bs.bs_stack_num_residuals(h) == 2
+        assert [bs.bs_stack_residual_shape(h, i) for i in range(2)] == wl.residual_shapes(layers, shape)
+        assert bs.bs_stack_num_index_outputs(h) == 2
+        assert bs.bs_stack_index_shape(h, 0) == (2, 6, 9, 12)
+        assert bs.bs_stack_index_shape(h, 1) == (2, 6, 4, 11)
+        assert _status(bs.bs_stack_index_shape, h, 2) == 11
+        assert _status(bs.bs_stack_residual_shape, h, -1) == 11
+        # not planned yet
+        assert _status(bs.bs_stack_plan_info, h) == 5
+        assert bs.bs_stack_workspace_bytes(h) == 0
+        assert _status(bs.bs_stack_run, h, 16, [16, 32], 64, None, 0, 0, 0) == 5
+    finally:
+        bs.bs_stack_destroy(h)
+
+
+def test_folded_batchnorm_matches_float64_definition():
+    p = wl.bn_params(32, 3)
+    h = bs.bs_stack_create([wl.relu(), p], (1, 32, 4, 4), "f32")
+    try:
+        scale, shift = bs.bs_stack_folded_bn(h, 1, 32)
+        s64 = p["gamma"].astype(np.float64) / np.sqrt(p["var"].astype(np.float64) + p["eps"])
+        assert np.array_equal(scale, s64.astype(np.float32))
+        assert np.array_equal(shift, (p["beta"].astype(np.float64) - p["mean"].astype(np.float64) * s64)
+                              .astype(np.float32))
+        assert _status(bs.bs_stack_folded_bn, h, 0, 32) == 11  # layer 0 is not a BatchNorm
+    finally:
+        bs.bs_stack_destroy(h)
+
+
+def test_parameters_are_copied_at_create():
+    p = wl.bn_params(8, 4)
+    h = bs.bs_stack_create([p], (1, 8, 4, 4), "f32")
+    before = bs.bs_stack_folded_bn(h, 0, 8)
+    for k in ("gamma", "beta", "mean", "var"):
+        p[k][:] = 123.0
+    after = bs.bs_stack_folded_bn(h, 0, 8)
+    bs.bs_stack_destroy(h)
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+
+
+def test_plan_option_validation():
+    h = bs.bs_stack_create([wl.relu()], (1, 4, 8, 8), "f32")
+    try:
+        assert _status(bs.bs_stack_plan, h, host_only=1, threads_per_group=100) == 3
+        assert _status(bs.bs_stack_plan, h, host_only=1, threads_per_group=1024) == 3
+        assert _status(bs.bs_stack_plan, h, host_only=1, force_variant=9) == 3
+        assert _status(bs.bs_stack_plan, h, host_only=1, max_lds_bytes=1 << 20) == 3
+        assert _status(bs.bs_stack_plan, h, host_only=1, max_steps_per_sequence=-1) == 3
+        bs.bs_stack_plan(h, host_only=1, threads_per_group=128)
+        info = bs.bs_stack_plan_info(h)
+        assert info["device_planned"] == 0 and info["n_sequences"] == 1
+        assert _status(bs.bs_stack_run, h, 16, None, 32, None, 0, 0, 0) == 5  # host-only plan cannot run
+        assert _status(bs.bs_stack_step_info, h, 5) == 11
+        assert _status(bs.bs_stack_sequence_info, h, 1) == 11
+        assert bs.bs_stack_operation_name(h, 0) == "ReLU" and bs.bs_stack_operation_name(h, 1) is None
+    finally:
+        bs.bs_stack_destroy(h)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(bs, "_lib", None)
+    monkeypatch.setattr(bs, "LIB_PATH", "/nonexistent/libbrainslug_hip.so")
+    with pytest.raises(RuntimeError):
+        bs.load()

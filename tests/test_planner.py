@@ -1,0 +1,191 @@
+"""Planner tests (host-only plans, no GPU): the collapse process of Section 4.1 --
+operations, steps, sequences -- and the tile geometry the LDS kernels rely on."""
+import numpy as np
+import pytest
+
+from oracle import breadth_first as bf
+from paper_1804_08378_amd import brainslug as bs
+from paper_1804_08378_amd import workloads as wl
+
+
+def plan(layers, shape, dtype="f32", **opts):
+    st = bs.Stack(layers, shape, dtype).plan(host_only=1, **opts)
+    info = st.info()
+    st.close()
+    return info
+
+
+def steps_of(info):
+    return [(s["first_operation"], s["n_operations"]) for s in info["steps"]]
+
+
+def test_listing2_example_partition():
+    """Listing 2: <MaxPooling, BatchNorm, ReLU> | <AvgPooling, AvgNormalization>."""
+    layers = [wl.maxpool(3, 1, 1), wl.bn_params(4, 0), wl.relu(), wl.avgpool(2, 2)]
+    info = plan(layers, (1, 4, 16, 16))
+    assert info["operations"] == ["MaxPooling", "BatchNorm", "ReLU", "AvgPooling", "AvgNormalization"]
+    assert steps_of(info) == [(0, 3), (3, 2)]
+    assert [s["pool_operation"] for s in info["steps"]] == [0, 3]
+    assert info["n_sequences"] == 1 and info["workspace_bytes"] == 0
+
+
+def test_step_rule_elementwise_always_joins_second_pool_opens_a_step():
+    layers = [wl.bn_params(4, 0), wl.relu(), wl.maxpool(2, 2), wl.relu(), wl.add(), wl.avgpool(2, 2),
+              wl.maxpool(2, 1), wl.relu()]
+    info = plan(layers, (1, 4, 32, 32))
+    # BN ReLU Max ReLU Add | AvgSum AvgNorm | Max ReLU
+    assert steps_of(info) == [(0, 5), (5, 2), (7, 2)]
+    # a stack without pooling is one step, one streaming sequence
+    info = plan([wl.bn_params(4, 0), wl.add(), wl.relu()], (1, 4, 8, 8))
+    assert steps_of(info) == [(0, 3)]
+    assert info["sequences"][0]["variant_name"] == "stream"
+
+
+@pytest.mark.parametrize("name,steps,variant", [
+    ("tiny", 1, "pool_direct"), ("vgg_a", 1, "pool_direct"), ("vgg_b", 1, "pool_direct"),
+    ("vgg_c", 1, "pool_direct"), ("resnet_stem", 1, "lds_tile"), ("resnet_tail", 1, "stream"),
+    ("densenet_dense", 1, "stream"), ("densenet_trans", 1, "pool_direct"), ("halo_stress", 2, "lds_tile"),
+])
+def test_baseline_configs_are_one_fused_sequence(name, steps, variant):
+    layers, shape, dtypes = wl.build(name)
+    for dt in dtypes:
+        info = plan(layers, shape, dt, num_cus=256)
+        assert info["n_steps"] == steps and info["n_sequences"] == 1
+        q = info["sequences"][0]
+        assert q["variant_name"] == variant
+        assert tuple(q["in_shape"]) == shape and tuple(q["out_shape"]) == wl.output_shape(layers, shape)
+        assert info["algorithmic_bytes"] == wl.algorithmic_bytes(layers, shape, dt)
+        assert q["lds_bytes"] <= 32 * 1024
+        assert q["grid"] >= 1
+        if variant == "lds_tile":
+            assert 1.0 <= q["redundancy"] < 1.1
+    if name == "halo_stress":
+        assert info["operations"] == ["BatchNorm", "ReLU", "AvgPooling", "AvgNormalization", "MaxPooling",
+                                      "BatchNorm", "ReLU"]
+        assert steps_of(info) == [(0, 4), (4, 3)]
+
+
+def _blocks(n, c=4):
+    return sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, i), wl.relu()] for i in range(n)), [])
+
+
+def test_steps_per_sequence_strategies():
+    """Section 5.1: 1 step per sequence, at most 5, unrestricted."""
+    layers = _blocks(12)
+    shape = (2, 4, 56, 56)
+    one = plan(layers, shape, max_steps_per_sequence=1)
+    five = plan(layers, shape, max_steps_per_sequence=5, max_lds_bytes=65536)
+    free = plan(layers, shape, max_lds_bytes=65536)
+    assert one["n_steps"] == five["n_steps"] == free["n_steps"] == 12
+    assert one["n_sequences"] == 12
+    assert all(q["n_steps"] <= 5 for q in five["sequences"]) and five["n_sequences"] >= 3
+    assert free["n_sequences"] <= five["n_sequences"]
+    assert one["workspace_bytes"] == 2 * 256 * ((2 * 4 * 56 * 56 * 4 + 255) // 256)
+    for info in (one, five, free):
+        assert sum(q["n_steps"] for q in info["sequences"]) == 12
+        assert [q["first_step"] for q in info["sequences"]] == list(
+            np.cumsum([0] + [q["n_steps"] for q in info["sequences"]][:-1]))
+
+
+def test_breadth_first_plan_is_one_sequence_per_layer():
+    layers, shape, _ = wl.build("halo_stress")
+    info = plan(layers, shape, breadth_first=1)
+    assert info["n_sequences"] == len(layers)
+    assert [q["n_layers"] for q in info["sequences"]] == [1] * len(layers)
+    assert info["workspace_bytes"] > 0
+
+
+def test_halo_grows_with_every_block_and_forces_a_new_sequence():
+    """Section 5.1: every padded block adds overlap; at a fixed on-chip budget an additional
+    sequence becomes necessary at some depth."""
+    shape = (1, 4, 64, 64)
+    lds, halos, seqs = [], [], []
+    for n in range(1, 9):
+        info = plan(_blocks(n), shape, max_lds_bytes=65536, tile_rows=8, tile_cols=16,
+                    force_variant=bs.BS_VARIANT_LDS_TILE)
+        q = info["sequences"][0]
+        if info["n_sequences"] == 1:
+            lds.append(q["lds_bytes"])
+            halos.append((q["halo_rows"], q["halo_cols"]))
+        seqs.append(plan(_blocks(n), shape, max_lds_bytes=8192)["n_sequences"])
+    assert all(b > a for a, b in zip(lds, lds[1:]))
+    assert [h[0] for h in halos] == [2 * (i + 1) for i in range(len(halos))]  # k=3, s=1: +2 rows per block
+    assert seqs[0] == 1 and seqs[-1] > 1 and all(b >= a for a, b in zip(seqs, seqs[1:]))
+
+
+def test_lds_budget_is_respected_and_no_fit_is_reported():
+    layers, shape, _ = wl.build("halo_stress")
+    for budget in (4096, 8192, 16384, 32768, 65536):
+        info = plan(layers, shape, max_lds_bytes=budget)
+        assert all(q["lds_bytes"] <= budget for q in info["sequences"])
+    with pytest.raises(bs.BrainSlugError) as e:
+        plan([wl.maxpool(31, 1, 15)], (1, 1, 64, 64), max_lds_bytes=1024)
+    assert e.value.status == 6
+
+
+def test_resource_example_ratio_is_k_squared():
+    """Section 4.1's example: a non-overlapping 3x3 pooling needs 3*3 times the output's data
+    as input."""
+    info = plan([wl.maxpool(3, 3)], (1, 4, 96, 96), force_variant=bs.BS_VARIANT_LDS_TILE,
+                tile_rows=8, tile_cols=16, max_lds_bytes=65536)
+    q = info["sequences"][0]
+    assert (q["halo_rows"], q["halo_cols"]) == (0, 0)
+    ratio = (q["lds_bytes"] / 4) / (8 * 16)
+    assert 9.0 <= ratio < 9.0 * 1.12  # row pitch slack only
+
+
+def test_tile_region_covers_the_true_dependency_cone():
+    """Brute force: perturb one input row / column at a time in the oracle and record which
+    output rows / columns move; the rectangle the planner reserves for an interior tile must be
+    exactly as tall as the set of input rows that tile depends on, and as wide up to strip
+    rounding."""
+    c = 2
+    layers = [wl.bn_params(c, 0), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1), wl.relu()]
+    shape = (1, c, 40, 36)
+    x = np.abs(wl.activation(shape, 5)) + 1.0  # positive: BN/ReLU/avg/max all pass a bump through
+    for l in layers:
+        if l["kind"] == "bn":
+            l["gamma"] = np.abs(l["gamma"]) + 0.5
+            l["mean"][:] = 0
+            l["beta"][:] = 0
+    ref, _, _ = bf.run_stack(layers, x)
+    th, tw = 4, 8
+    info = plan(layers, shape, force_variant=bs.BS_VARIANT_LDS_TILE, tile_rows=th, tile_cols=tw,
+                max_lds_bytes=65536)
+    q = info["sequences"][0]
+    for axis, tile, halo, size in ((2, th, q["halo_rows"], 40), (3, tw, q["halo_cols"], 36)):
+        dep = []
+        for i in range(size):
+            xp = x.copy()
+            sl = [slice(None)] * 4
+            sl[axis] = i
+            xp[tuple(sl)] += 100.0
+            out, _, _ = bf.run_stack(layers, xp)
+            moved = np.nonzero((out != ref).any(axis=tuple(a for a in range(4) if a != axis)))[0]
+            dep.append(set(moved.tolist()))
+        t = 1  # an interior tile
+        outs = set(range(t * tile, (t + 1) * tile))
+        needed = [i for i in range(size) if dep[i] & outs]
+        assert needed == list(range(needed[0], needed[-1] + 1))
+        reserved = tile * 2 + halo
+        if axis == 2:
+            assert reserved == len(needed), (len(needed), reserved)
+        else:  # column extents are rounded up to the four-output strips of the pooling phases
+            assert len(needed) <= reserved <= len(needed) + 3, (len(needed), reserved)
+
+
+def test_index_output_in_mid_sequence_needs_full_coverage():
+    """A max pool whose indices are wanted may stay inside a sequence only if the windows of
+    the later pooling operations cover its whole output; otherwise the sequence ends there."""
+    covered = [wl.maxpool(3, 1, 1, True), wl.relu(), wl.maxpool(3, 2, 1)]
+    gaps = [wl.maxpool(3, 1, 1, True), wl.relu(), wl.maxpool(2, 3, 0)]
+    assert plan(covered, (1, 2, 32, 32))["n_sequences"] == 1
+    assert plan(gaps, (1, 2, 32, 32))["n_sequences"] == 2
+
+
+def test_capacity_splits_keep_every_operation():
+    layers = [wl.relu()] * 40 + [wl.maxpool(2, 2)] + [wl.add()] * 9
+    info = plan(layers, (1, 2, 16, 16))
+    assert info["n_operations"] == 50
+    assert sum(s["n_operations"] for s in info["steps"]) == 50
+    assert sum(q["n_layers"] for q in info["sequences"]) == 50
