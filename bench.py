@@ -75,15 +75,26 @@ class StackBench:
 
 
 def time_steps(stacks, which, steps, warmup):
-    """Returns (wall ms per step, {stack name: mean kernel-region ms from HIP events})."""
+    """K steps (each: every stack once, rotating buffers).
+
+    Returns (wall ms per step, {name: mean ms}, {name: min ms}).  The wall time brackets exactly
+    `steps` steps with a device synchronisation on both sides and nothing else in between; the
+    per-stack figures come from a second pass with one HIP event pair around every launch (on
+    torch's current stream, the stream the kernels are launched on).
+    """
     import torch
 
     for _ in range(warmup):
         for sb in stacks:
             sb.launch(which)
     torch.cuda.synchronize()
-    ev = {sb.name: [] for sb in stacks}
     t0 = time.perf_counter()
+    for _ in range(steps):
+        for sb in stacks:
+            sb.launch(which)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ev = {sb.name: [] for sb in stacks}
     for _ in range(steps):
         for sb in stacks:
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -92,10 +103,26 @@ def time_steps(stacks, which, steps, warmup):
             b.record()
             ev[sb.name].append((a, b))
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
     per = {k: sum(a.elapsed_time(b) for a, b in v) / len(v) for k, v in ev.items()}
     mins = {k: min(a.elapsed_time(b) for a, b in v) for k, v in ev.items()}
     return (t1 - t0) * 1e3 / steps, per, mins
+
+
+def time_back_to_back(sb, which, launches):
+    """Average duration of one launch of `sb` when `launches` of them run back to back between
+    one HIP event pair: the kernel's own duration plus the gap to the next launch."""
+    import torch
+
+    for _ in range(3):
+        sb.launch(which)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(launches):
+        sb.launch(which)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / launches
 
 
 def cpu_baseline(names, dtype, batch):
@@ -125,6 +152,12 @@ def main():
     ap.add_argument("--all", action="store_true", help="also report every BASELINE config (stderr)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-batch", type=int, default=8)
+    ap.add_argument("--no-baseline", action="store_true",
+                    help="skip the layer-by-layer HIP plan (its pooling layer runs the same kernel symbol "
+                         "as the fused stack, which would mix the two in a rocprofv3 --stats summary)")
+    ap.add_argument("--probe", type=int, default=0, metavar="N",
+                    help="counter probe for rocprofv3 --pmc: N launches of a plain copy of known size, "
+                         "then N launches of each VGG stack; no timing, no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (the path shards over the batch with no "
@@ -141,13 +174,31 @@ def main():
     bs.load()
     log(bs.bs_version(), "|", torch.cuda.get_device_name(0))
 
+    if args.probe:
+        # a copy of exactly 256 MiB in and 256 MiB out calibrates the byte counters
+        n = (256 << 20) // 4
+        src, dst = torch.ones(n, device="cuda"), torch.empty(n, device="cuda")
+        for _ in range(args.probe):
+            torch.mul(src, 1.0, out=dst)  # an element-wise kernel: reads n floats, writes n floats
+        torch.cuda.synchronize()
+        for name in wl.VGG_STACKS:
+            sb = StackBench(name, "f32")
+            for _ in range(args.probe):
+                sb.launch("fused")
+            torch.cuda.synchronize()
+            log("probe", name, "algorithmic bytes per launch", sb.bytes)
+        return
+
     stacks = [StackBench(n, "f32") for n in wl.VGG_STACKS]
     step_bytes = sum(sb.bytes for sb in stacks)
     ms, per, mins = time_steps(stacks, "fused", args.steps, args.warmup)
-    ms_lbl, per_lbl, _ = time_steps(stacks, "lbl", max(10, args.steps // 4), max(2, args.warmup // 2))
+    if args.no_baseline:
+        ms_lbl = float("nan")
+    else:
+        ms_lbl, per_lbl, _ = time_steps(stacks, "lbl", max(10, args.steps // 4), max(2, args.warmup // 2))
     value = step_bytes / (ms * 1e-3) / 1e9
     dom = stacks[0]
-    dom_ms = per[dom.name]
+    dom_ms = time_back_to_back(dom, "fused", max(20, args.steps // 2))
     achieved = dom.bytes / (dom_ms * 1e-3) / 1e9
     out = {
         "metric": "fused-stack effective HBM GB/s (algorithmic bytes / time), 1 GPU",
@@ -159,10 +210,10 @@ def main():
                    "rotation_sets": [sb.sets for sb in stacks]},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "images_per_s": round(dom.images / (ms * 1e-3), 1),
-        "speedup_vs_layer_by_layer": round(ms_lbl / ms, 3),
-        "layer_by_layer": {"ms_per_step": round(ms_lbl, 4),
-                           "GBps_of_its_own_traffic": round(sum(sb.lbl_bytes for sb in stacks) /
-                                                            (ms_lbl * 1e-3) / 1e9, 1)},
+        "speedup_vs_layer_by_layer": None if args.no_baseline else round(ms_lbl / ms, 3),
+        "layer_by_layer": None if args.no_baseline else {
+            "ms_per_step": round(ms_lbl, 4),
+            "GBps_of_its_own_traffic": round(sum(sb.lbl_bytes for sb in stacks) / (ms_lbl * 1e-3) / 1e9, 1)},
         "per_stack": {sb.name: {"ms_mean": round(per[sb.name], 4), "ms_min": round(mins[sb.name], 4),
                                 "GBps": round(sb.bytes / (per[sb.name] * 1e-3) / 1e9, 1),
                                 "variant": [q["variant_name"] for q in sb.info["sequences"]]}
@@ -170,7 +221,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "pool_direct_kernel<f32,4,2,2> on 32x64x224x224",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "bytes_per_launch": dom.bytes, "avg_launch_ms": round(dom_ms, 4)},
+                     "bytes_per_launch": dom.bytes, "avg_launch_ms": round(dom_ms, 4),
+                     "avg_launch_ms_single_event_pair": round(per[dom.name], 4)},
         "context": PAPER_CONTEXT,
     }
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
