@@ -111,7 +111,8 @@ typedef enum bs_variant {
     BS_VARIANT_AUTO = 0,
     BS_VARIANT_STREAM = 1,      /* element-wise only: 128-bit streaming, registers only         */
     BS_VARIANT_POOL_DIRECT = 2, /* one step, disjoint windows (k == s, p == 0): registers only   */
-    BS_VARIANT_LDS_TILE = 3     /* tiles with halos staged in LDS, ping-pong buffers, barriers   */
+    BS_VARIANT_LDS_TILE = 3,    /* tiles with halos staged in LDS, ping-pong buffers, barriers   */
+    BS_VARIANT_POOL_ROWS = 4    /* one step, overlapping / padded windows: rows slide in registers */
 } bs_variant;
 
 /*
@@ -170,7 +171,6 @@ typedef struct bs_sequence_info {
     double redundancy;               /* elements loaded (with halos) / elements of the input */
 } bs_sequence_info;
 
-/* Names of the basic operations a plan lists (bs_stack_operation_name). */
 
 /*
  * Create a stack from `n_layers` layer descriptions and the NCHW input shape

@@ -135,6 +135,22 @@ struct PoolDirectK {
     FastDiv div_c;
 };
 
+struct PoolRowsK {
+    const void *in;
+    void *out;
+    const float *params;
+    int32_t *idx;
+    int32_t n_pre, n_post;
+    EwOp pre[K_MAX_EW], post[K_MAX_EW];
+    PoolK pool;
+    int32_t C, H, W, Ho, Wo;
+    int32_t rc;       // output rows one lane walks down
+    int32_t chunks;   // chunks per plane = ceil(Ho / rc)
+    int32_t cbs;      // 128-bit column blocks per input row = W / vec
+    uint32_t total;   // lanes with work = planes * chunks * cbs
+    FastDiv div_cbs, div_chunks, div_c;
+};
+
 // Origin (global row / column of LDS cell 0,0) of every level's region for tile (ti, tj).
 // Used by the kernel and, with the same code, by the planner's bounds audit.
 struct Origins {
@@ -187,6 +203,7 @@ struct Sequence {
     // argument blocks; pointers are filled in at run time
     StreamK stream{};
     PoolDirectK direct{};
+    PoolRowsK rows{};
     LdsSeqK lds{};
 };
 
@@ -243,6 +260,9 @@ void free_params(bs_stack *s);
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
                           const void *const *res, int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
+// bs_rows.hip
+bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);
+bs_status launch_rows(const PoolRowsK &k, bool bf16, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
 bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
 

@@ -331,6 +331,14 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         else launch_direct<false, 4>(k, grid, block, st);
         break;
     }
+    case BS_VARIANT_POOL_ROWS: {
+        PoolRowsK k = q.rows;
+        k.in = in; k.out = out; k.params = s->dev_params;
+        k.idx = ip[0];
+        const bs_status ls = launch_rows(k, bf16, q.grid, q.threads, stream);
+        if (ls != BS_OK) return ls;
+        break;
+    }
     case BS_VARIANT_LDS_TILE: {
         LdsSeqK k = q.lds;
         k.in = in; k.out = out; k.params = s->dev_params;

@@ -301,10 +301,13 @@ static bool direct_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops
 
 // Resource consumption of a candidate sequence (Section 4.1): the on-chip bytes of the
 // smallest useful tile, including the overlap that padding / k > s adds at every level.
+static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill);
+
 static uint64_t seq_min_lds(const bs_stack *s, int32_t first_op, int32_t n_ops, int32_t threads)
 {
     if (count_pools(s, first_op, n_ops) == 0) return 0;
     if (direct_applicable(s, first_op, n_ops) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
+    if (rows_applicable(s, first_op, n_ops, nullptr) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
     const Op &last = s->ops[first_op + n_ops - 1];
     int32_t th, tw;
     min_tile(last.out_h, last.out_w, threads, th, tw);
@@ -414,6 +417,78 @@ static void plan_direct(const bs_stack *s, Sequence &q)
     q.tile_rows = q.tile_cols = 0;
     q.planes_per_group = 0;
     q.n_levels = 1;
+}
+
+// One pooling operation with overlapping / padded windows, BatchNorm and ReLU only around it,
+// in a shape the rows kernel is instantiated for.
+static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
+{
+    if (count_pools(s, first_op, n_ops) != 1) return false;
+    const int32_t vec = vec_of(s);
+    Sequence tmp;
+    Sequence &q = fill ? *fill : tmp;
+    PoolRowsK k{};
+    bool seen = false;
+    for (int32_t i = first_op; i < first_op + n_ops; ++i) {
+        const Op &op = s->ops[i];
+        if (!op_is_elementwise(op.kind)) {
+            if (op.in_w % vec != 0 || vec % op.sw != 0 || op.kw - op.sw - op.pw < 0) return false;
+            k.pool = make_pool(op, nullptr, q);
+            k.H = op.in_h; k.W = op.in_w; k.Ho = op.out_h; k.Wo = op.out_w;
+            seen = true;
+        } else if (op.kind != OP_AVGNORM) {
+            if (op.kind == OP_ADD) return false;
+            if ((seen ? k.n_post : k.n_pre) >= K_MAX_EW) return false;
+            if (seen) fill_ew(s, op, q, k.post[k.n_post++]);
+            else fill_ew(s, op, q, k.pre[k.n_pre++]);
+        }
+    }
+    if (!rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) return false;
+    if (fill) fill->rows = k;
+    return true;
+}
+
+static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, const Limits &lim)
+{
+    q.variant = BS_VARIANT_POOL_ROWS;
+    q.n_idx = 0;
+    rows_applicable(s, q.first_op, q.n_ops, &q);
+    PoolRowsK &k = q.rows;
+    const int32_t vec = vec_of(s);
+    q.vec = vec;
+    q.threads = std::min(q.threads, 256);
+    k.C = (int32_t)q.in_shape[1];
+    const int64_t planes = q.in_shape[0] * q.in_shape[1];
+    k.cbs = k.W / vec;
+    // rows per lane: as long as possible (each chunk re-reads kh - sh rows of its neighbour)
+    // while leaving about two full-occupancy rounds of waves for the chip
+    int32_t rc = k.Ho;
+    const double want_lanes = 2.0 * 2048.0 * std::max(1, lim.num_cus);
+    while (rc > 4 && (double)planes * k.cbs * ((k.Ho + rc - 1) / rc) < want_lanes) rc = (rc + 1) / 2;
+    if (o.tile_rows > 0) rc = std::min(o.tile_rows, k.Ho);
+    k.rc = std::max(1, rc);
+    k.chunks = (k.Ho + k.rc - 1) / k.rc;
+    k.total = (uint32_t)(planes * k.chunks * k.cbs);
+    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+    k.div_c = make_fastdiv((uint32_t)k.C);
+    q.grid = ((int64_t)k.total + q.threads - 1) / q.threads;
+    q.lds_bytes = 0;
+    q.tile_rows = k.rc;
+    q.tile_cols = k.Wo;
+    q.planes_per_group = 0;
+    q.n_levels = 1;
+    q.halo_rows = std::max(0, k.pool.kh - k.pool.sh);
+    q.halo_cols = 0;
+    // rows loaded per plane / rows of the plane
+    double rows_loaded = 0;
+    for (int32_t ch = 0; ch < k.chunks; ++ch) {
+        const int32_t a = ch * k.rc, b = std::min(k.Ho, a + k.rc);
+        const int32_t lo = std::max(0, a * k.pool.sh - k.pool.ph);
+        const int32_t hi = std::min(k.H, (b - 1) * k.pool.sh - k.pool.ph + k.pool.kh);
+        rows_loaded += std::max(0, hi - lo);
+    }
+    q.redundancy = rows_loaded / (double)k.H;
 }
 
 static bool audit_lds(const Sequence &q);
@@ -680,6 +755,8 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             plan_stream(s, q);
         } else if (direct_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {
             plan_direct(s, q);
+        } else if (rows_applicable(s, q.first_op, q.n_ops, nullptr) && o.force_variant != BS_VARIANT_LDS_TILE) {
+            plan_rows(s, q, o, lim);
         } else {
             st = plan_lds(s, q, o, lim);
         }
@@ -713,7 +790,7 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (o.threads_per_group != 0 &&
         (o.threads_per_group < 64 || o.threads_per_group > 512 || o.threads_per_group % 64 != 0))
         return BS_ERR_PARAM;
-    if (o.force_variant < 0 || o.force_variant > BS_VARIANT_LDS_TILE) return BS_ERR_PARAM;
+    if (o.force_variant < 0 || o.force_variant > BS_VARIANT_POOL_ROWS) return BS_ERR_PARAM;
     if (o.max_lds_bytes > 64 * 1024) return BS_ERR_PARAM;
 
     stack->planned = stack->device_planned = false;

@@ -1,0 +1,333 @@
+// pool_rows_kernel: one pooling operation with overlapping or padded windows (plus the
+// element-wise operations before and after it) without LDS: the "non-stacked" pooling
+// building block of Section 4.4, where values pass from operation to operation directly
+// (Section 4.1, single-step sequence).
+//
+// A lane owns one 128-bit column block of the input plane (VEC columns -> VO = VEC / sw
+// outputs per output row) and walks down a chunk of rc output rows.  It keeps the kh input
+// rows of the current windows in registers (after the leading element-wise operations), so
+// every input row is loaded once per lane: per output row it loads only the sh new rows --
+// one 128-bit vector each, plus the pw columns to the left and kw - sw - pw columns to the
+// right of its block as scalar loads that hit the lines its neighbours fetch.  Cells outside
+// the plane are the pooling operation's padding (-inf / +0) and are never computed from
+// earlier layers.  Loads for the next output row are issued before the current one is
+// reduced.  Only the rows shared by two vertically adjacent chunks are read twice.
+//
+// The pooling shape and the element-wise lists are template arguments; the planner uses this
+// kernel only for the signatures instantiated in the table at the end (rows_supported()).
+#include <type_traits>
+
+#include "bs_device.h"
+
+namespace bs {
+
+template <int KIND, int KH, int KW, int SH, int SW, int PH, int PW>
+struct RowsSpec {
+    static constexpr int kind = KIND, kh = KH, kw = KW, sh = SH, sw = SW, ph = PH, pw = PW;
+};
+
+// element-wise list codes (base 4 digits, first operation lowest): see rows_ew_code()
+constexpr int RW_NONE = 0;
+constexpr int RW_BN_RELU = OP_BN + 4 * OP_RELU;
+
+template <int CODE>
+struct RowsEw {
+    static constexpr int count()
+    {
+        int n = 0, c = CODE;
+        while (c) { ++n; c /= 4; }
+        return n;
+    }
+    static constexpr int n = count();
+    __host__ __device__ static constexpr int kind(int j)
+    {
+        int c = CODE;
+        for (int i = 0; i < j; ++i) c /= 4;
+        return c % 4;
+    }
+};
+
+template <class EW>
+struct RowsParams {
+    float sc[EW::n > 0 ? EW::n : 1], sh[EW::n > 0 ? EW::n : 1];
+};
+
+template <class EW>
+BS_DEV void rows_load_params(const EwOp *ew, const float *__restrict__ params, int32_t C, int32_t c,
+                             RowsParams<EW> &p)
+{
+#pragma unroll
+    for (int j = 0; j < EW::n; ++j) {
+        p.sc[j] = 1.0f;
+        p.sh[j] = 0.0f;
+        if (EW::kind(j) == OP_BN) {
+            p.sc[j] = params[ew[j].arg + c];
+            p.sh[j] = params[ew[j].arg + C + c];
+        }
+    }
+}
+
+// BatchNorm / ReLU lists only (a residual Add would need its own halo loads; such stacks
+// take the LDS path).
+template <bool BF16, class EW, int N>
+BS_DEV void rows_apply(float (&x)[N], const RowsParams<EW> &p)
+{
+#pragma unroll
+    for (int j = 0; j < EW::n; ++j) {
+        if (EW::kind(j) == OP_BN) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fmaf(x[i], p.sc[j], p.sh[j]));
+        } else {
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = __builtin_fmaxf(x[i], 0.0f);  // NaN, -0 -> +0
+        }
+    }
+}
+
+template <bool BF16, int VEC, class P, int EWPRE, int EWPOST, bool WANT_IDX>
+__global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
+{
+    constexpr int KH = P::kh, KW = P::kw, SH = P::sh, SW = P::sw, PH = P::ph, PW = P::pw;
+    constexpr int VO = VEC / SW;           // outputs per lane per output row
+    constexpr int NL = PW;                 // columns left of the block
+    constexpr int NX = KW - SW - PW;       // columns right of the block
+    constexpr int NC = NL + VEC + NX;      // columns the VO windows span
+    constexpr int NS = SH < KH ? SH : KH;  // new input rows per output row
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr bool IS_MAX = P::kind == OP_MAXPOOL;
+    static_assert(VEC % SW == 0 && NX >= 0 && NL >= 0, "unsupported pooling shape");
+    using EWP = RowsEw<EWPRE>;
+    using EWQ = RowsEw<EWPOST>;
+    const float padv = IS_MAX ? -INFINITY : 0.0f;
+
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = i < k.total;
+    i = live ? i : 0u;
+    const uint32_t t = fdiv(i, k.div_cbs);
+    const int32_t j = (int32_t)(i - t * (uint32_t)k.cbs);
+    const uint32_t plane = fdiv(t, k.div_chunks);
+    const int32_t chunk = (int32_t)(t - plane * (uint32_t)k.chunks);
+    const int32_t c = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+
+    RowsParams<EWP> pp;
+    RowsParams<EWQ> qp;
+    rows_load_params<EWP>(k.pre, k.params, k.C, c, pp);
+    rows_load_params<EWQ>(k.post, k.params, k.C, c, qp);
+
+    const char *inp = static_cast<const char *>(k.in) + (size_t)plane * (size_t)(k.H * k.W) * ES;
+    const int32_t col0 = j * VEC;  // first column of the lane's block
+    bool lin[NL > 0 ? NL : 1], xin[NX > 0 ? NX : 1];
+#pragma unroll
+    for (int n = 0; n < NL; ++n) lin[n] = col0 - NL + n >= 0;
+#pragma unroll
+    for (int n = 0; n < NX; ++n) xin[n] = col0 + VEC + n < k.W;
+
+    struct RowRaw {
+        Raw<BF16, VEC> v;
+        Raw<BF16, 1> l[NL > 0 ? NL : 1], x[NX > 0 ? NX : 1];
+        bool ok;
+    };
+    // issue the loads of input row ih (clamped to a safe address when the row is padding)
+    auto fetch = [&](int32_t ih, RowRaw &r) {
+        r.ok = ih >= 0 && ih < k.H;
+        const uint32_t rowoff = r.ok ? (uint32_t)(ih * k.W) : 0u;
+        r.v = load_raw<BF16, VEC>(inp, rowoff + (uint32_t)col0);
+#pragma unroll
+        for (int n = 0; n < NL; ++n) r.l[n] = load_raw<BF16, 1>(inp, lin[n] ? rowoff + (uint32_t)(col0 - NL + n) : 0u);
+#pragma unroll
+        for (int n = 0; n < NX; ++n) r.x[n] = load_raw<BF16, 1>(inp, xin[n] ? rowoff + (uint32_t)(col0 + VEC + n) : 0u);
+    };
+    // registers -> window row: leading element-wise operations, then padding
+    auto settle = [&](const RowRaw &r, float (&w)[NC]) {
+        float xv[VEC];
+        unpack<BF16, VEC>(r.v, xv);
+#pragma unroll
+        for (int n = 0; n < VEC; ++n) w[NL + n] = xv[n];
+#pragma unroll
+        for (int n = 0; n < NL; ++n) {
+            float one[1];
+            unpack<BF16, 1>(r.l[n], one);
+            w[n] = one[0];
+        }
+#pragma unroll
+        for (int n = 0; n < NX; ++n) {
+            float one[1];
+            unpack<BF16, 1>(r.x[n], one);
+            w[NL + VEC + n] = one[0];
+        }
+        rows_apply<BF16, EWP, NC>(w, pp);
+#pragma unroll
+        for (int n = 0; n < NL; ++n) w[n] = (r.ok && lin[n]) ? w[n] : padv;
+#pragma unroll
+        for (int n = 0; n < VEC; ++n) w[NL + n] = r.ok ? w[NL + n] : padv;
+#pragma unroll
+        for (int n = 0; n < NX; ++n) w[NL + VEC + n] = (r.ok && xin[n]) ? w[NL + VEC + n] : padv;
+    };
+
+    const int32_t oh0 = chunk * k.rc;
+    const int32_t oh1 = live ? min(k.Ho, oh0 + k.rc) : oh0;
+    const int32_t ow0 = j * VO;
+    const bool vec_store = (k.Wo % VO) == 0 && ow0 + VO <= k.Wo;
+    const uint32_t oplane = plane * (uint32_t)(k.Ho * k.Wo);
+
+    float win[KH][NC];
+    {
+        RowRaw r[KH];
+#pragma unroll
+        for (int dh = 0; dh < KH; ++dh) fetch(oh0 * SH - PH + dh, r[dh]);
+#pragma unroll
+        for (int dh = 0; dh < KH; ++dh) settle(r[dh], win[dh]);
+    }
+    for (int32_t oh = oh0; oh < oh1; ++oh) {
+        const int32_t h0 = oh * SH - PH;
+        // loads for the next output row first
+        RowRaw nr[NS];
+#pragma unroll
+        for (int n = 0; n < NS; ++n) fetch(oh + 1 < oh1 ? h0 + SH + (KH - NS) + n : -1, nr[n]);
+
+        float y[VO];
+        int32_t yi[VO];
+#pragma unroll
+        for (int e = 0; e < VO; ++e) {
+            const int32_t w0 = col0 - PW + e * SW;
+            if (IS_MAX) {
+                float best = -INFINITY;
+                int32_t bi = max(h0, 0) * k.W + max(w0, 0);  // first in-range cell
+#pragma unroll
+                for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw) {
+                        const float v = win[dh][e * SW + dw];
+                        if constexpr (WANT_IDX) {
+                            const bool g = v > best;
+                            best = g ? v : best;
+                            bi = g ? (h0 + dh) * k.W + w0 + dw : bi;
+                        } else {
+                            best = __builtin_fmaxf(best, v);
+                        }
+                    }
+                y[e] = best;
+                yi[e] = bi;
+            } else {
+                float sum = 0.0f;
+#pragma unroll
+                for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw) sum = sum + win[dh][e * SW + dw];
+                float inv = k.pool.inv_kk;
+                if (!k.pool.count_include_pad) {
+                    const int32_t nr_ = min(h0 + KH, k.H) - max(h0, 0);
+                    const int32_t nc_ = min(w0 + KW, k.W) - max(w0, 0);
+                    inv = 1.0f / (float)max(nr_ * nc_, 1);
+                }
+                y[e] = round_store<BF16>(sum * inv);
+                yi[e] = 0;
+            }
+        }
+        rows_apply<BF16, EWQ, VO>(y, qp);
+        const uint32_t ooff = oplane + (uint32_t)(oh * k.Wo + ow0);
+        if (vec_store) {
+            store_elems<BF16, VO>(k.out, ooff, y);
+            if constexpr (WANT_IDX) {
+                if (k.idx) {
+#pragma unroll
+                    for (int e = 0; e < VO; ++e) k.idx[ooff + e] = yi[e];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < VO; ++e)
+                if (ow0 + e < k.Wo) {
+                    const float one[1] = {y[e]};
+                    store_elems<BF16, 1>(k.out, ooff + e, one);
+                    if constexpr (WANT_IDX) {
+                        if (k.idx) k.idx[ooff + e] = yi[e];
+                    }
+                }
+        }
+        // slide the window down by sh rows
+#pragma unroll
+        for (int dh = 0; dh + SH < KH; ++dh)
+#pragma unroll
+            for (int n = 0; n < NC; ++n) win[dh][n] = win[dh + SH][n];
+#pragma unroll
+        for (int n = 0; n < NS; ++n) settle(nr[n], win[KH - NS + n]);
+    }
+}
+
+// =============================================================================
+// Signature table, applicability test and launcher.
+// =============================================================================
+using RMax3s2p1 = RowsSpec<OP_MAXPOOL, 3, 3, 2, 2, 1, 1>;
+using RMax3s2p0 = RowsSpec<OP_MAXPOOL, 3, 3, 2, 2, 0, 0>;
+using RMax3s1p1 = RowsSpec<OP_MAXPOOL, 3, 3, 1, 1, 1, 1>;
+using RAvg3s1p1 = RowsSpec<OP_AVGSUM, 3, 3, 1, 1, 1, 1>;
+
+static int rows_ew_code(const EwOp *ew, int n)
+{
+    int code = 0, mul = 1;
+    for (int j = 0; j < n; ++j) {
+        if (ew[j].kind != OP_BN && ew[j].kind != OP_RELU) return -1;
+        code += ew[j].kind * mul;
+        mul *= 4;
+    }
+    return code;
+}
+
+template <class P>
+static bool rows_pool_is(const PoolK &q)
+{
+    return q.kind == P::kind && q.kh == P::kh && q.kw == P::kw && q.sh == P::sh && q.sw == P::sw &&
+           q.ph == P::ph && q.pw == P::pw;
+}
+
+// visit every instantiated signature; F(spec tag, pre code, post code) returns true to stop
+template <class F>
+static bool rows_for_each_signature(F &&f)
+{
+    return f(RMax3s2p1{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RMax3s2p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RMax3s2p0{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RMax3s2p0{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RMax3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_BN_RELU>{}) ||
+           f(RMax3s1p1{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RMax3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RAvg3s1p1{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RAvg3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{});
+}
+
+bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post)
+{
+    const int cp = rows_ew_code(pre, n_pre), cq = rows_ew_code(post, n_post);
+    if (cp < 0 || cq < 0) return false;
+    return rows_for_each_signature([&](auto spec, auto pc, auto qc) {
+        using P = decltype(spec);
+        return rows_pool_is<P>(pool) && cp == decltype(pc)::value && cq == decltype(qc)::value;
+    });
+}
+
+template <bool BF16, int VEC>
+static bool rows_launch_t(const PoolRowsK &k, bool want_idx, dim3 grid, dim3 block, hipStream_t st)
+{
+    const int cp = rows_ew_code(k.pre, k.n_pre), cq = rows_ew_code(k.post, k.n_post);
+    return rows_for_each_signature([&](auto spec, auto pc, auto qc) {
+        using P = decltype(spec);
+        constexpr int PC = decltype(pc)::value, QC = decltype(qc)::value;
+        if (!rows_pool_is<P>(k.pool) || cp != PC || cq != QC) return false;
+        if (want_idx) pool_rows_kernel<BF16, VEC, P, PC, QC, true><<<grid, block, 0, st>>>(k);
+        else pool_rows_kernel<BF16, VEC, P, PC, QC, false><<<grid, block, 0, st>>>(k);
+        return true;
+    });
+}
+
+bs_status launch_rows(const PoolRowsK &k, bool bf16, int64_t grid_n, int32_t threads, void *stream)
+{
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
+    const bool want_idx = k.idx != nullptr && k.pool.kind == OP_MAXPOOL;
+    const bool ok = bf16 ? rows_launch_t<true, 8>(k, want_idx, grid, block, st)
+                         : rows_launch_t<false, 4>(k, want_idx, grid, block, st);
+    return ok ? BS_OK : BS_ERR_UNSUPPORTED;
+}
+
+}  // namespace bs

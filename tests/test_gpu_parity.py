@@ -234,3 +234,33 @@ def test_config_full_size(name, dtype):
     if any(l["kind"] == "maxpool" for l in layers):
         layers, x, res = wl.inputs_for(name, 0, dtype, indices=True)
         check(layers, x, res, dtype, f"{name}/full+indices")
+
+
+# ------------------------------------------------------------------ rows kernel (no LDS)
+def _rows_stacks(c):
+    return {
+        "stem": [wl.bn_params(c, 60), wl.relu(), wl.maxpool(3, 2, 1, True)],
+        "max3s2p1": [wl.maxpool(3, 2, 1, True)],
+        "stem_nopad": [wl.bn_params(c, 61), wl.relu(), wl.maxpool(3, 2, 0, True)],
+        "max3s2p0": [wl.maxpool(3, 2, 0, False)],
+        "block": [wl.maxpool(3, 1, 1, True), wl.bn_params(c, 62), wl.relu()],
+        "bn_relu_max3s1": [wl.bn_params(c, 63), wl.relu(), wl.maxpool(3, 1, 1, False)],
+        "max3s1p1": [wl.maxpool(3, 1, 1, True)],
+        "bn_relu_avg3s1": [wl.bn_params(c, 64), wl.relu(), wl.avgpool(3, 1, 1, True)],
+        "avg3s1p1": [wl.avgpool(3, 1, 1, True)],
+    }
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 12, 16), (1, 2, 9, 8), (3, 5, 33, 24), (1, 4, 64, 64), (1, 1, 3, 8)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pool_rows_kernel(shape, dtype):
+    """Single pooling step with overlapping / padded windows through the register-sliding
+    rows kernel, for several chunk lengths (1 row per lane, ragged, whole plane)."""
+    for name, layers in _rows_stacks(shape[1]).items():
+        x = wl.activation(shape, 70, dtype)
+        for rc in (0, 1, 3, 1000):
+            info = check(layers, x, [], dtype, f"rows/{name}{shape}/rc{rc}", tile_rows=rc)
+            assert info["sequences"][0]["variant_name"] == "pool_rows", name
+        # the same stack through the LDS kernels agrees as well
+        info = check(layers, x, [], dtype, f"rows/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
+        assert info["sequences"][0]["variant_name"] == "lds_tile"
