@@ -58,12 +58,28 @@ struct Raw {
     type q;
 };
 
-template <bool BF16, int N>
+// NT: non-temporal (streaming) load for data that is read exactly once; leave it off where
+// neighbouring lanes or tiles re-read the same cache lines.
+template <bool BF16, int N, bool NT = false>
 BS_DEV Raw<BF16, N> load_raw(const void *base, uint32_t elem)
 {
     using T = typename Raw<BF16, N>::type;
     Raw<BF16, N> r;
-    r.q = *reinterpret_cast<const T *>(static_cast<const char *>(base) + (size_t)elem * (BF16 ? 2 : 4));
+    const char *ptr = static_cast<const char *>(base) + (size_t)elem * (BF16 ? 2 : 4);
+    constexpr int BYTES = N * (BF16 ? 2 : 4);
+    if constexpr (!NT) {
+        r.q = *reinterpret_cast<const T *>(ptr);
+    } else if constexpr (BYTES == 16) {
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const u4 t = __builtin_nontemporal_load(reinterpret_cast<const u4 *>(ptr));
+        r.q = make_uint4(t.x, t.y, t.z, t.w);
+    } else if constexpr (BYTES == 8) {
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        const u2 t = __builtin_nontemporal_load(reinterpret_cast<const u2 *>(ptr));
+        r.q = make_uint2(t.x, t.y);
+    } else {
+        r.q = __builtin_nontemporal_load(reinterpret_cast<const T *>(ptr));
+    }
     return r;
 }
 
@@ -93,14 +109,21 @@ BS_DEV void unpack(const Raw<BF16, N> &r, float (&v)[N])
 }
 
 // Store N consecutive elements (N * element size is 2, 4, 8 or 16 bytes, naturally aligned).
+// Outputs are written once and not read again by the kernel: vector stores are non-temporal.
 template <bool BF16, int N>
 BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
 {
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
     if constexpr (!BF16) {
         float *p = static_cast<float *>(base) + elem;
-        if constexpr (N == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-        else if constexpr (N == 2) *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
-        else {
+        if constexpr (N == 4) {
+            const u4 t = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+            __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));
+        } else if constexpr (N == 2) {
+            const u2 t = {__float_as_uint(v[0]), __float_as_uint(v[1])};
+            __builtin_nontemporal_store(t, reinterpret_cast<u2 *>(p));
+        } else {
 #pragma unroll
             for (int i = 0; i < N; ++i) p[i] = v[i];
         }
@@ -111,15 +134,20 @@ BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
 #pragma unroll
             for (int i = 0; i < N / 2; ++i)
                 w[i] = (uint32_t)bf16_bits(v[2 * i]) | ((uint32_t)bf16_bits(v[2 * i + 1]) << 16);
-            if constexpr (N == 8) *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
-            else if constexpr (N == 4) *reinterpret_cast<uint2 *>(p) = make_uint2(w[0], w[1]);
-            else *reinterpret_cast<uint32_t *>(p) = w[0];
+            if constexpr (N == 8) {
+                const u4 t = {w[0], w[1], w[2], w[3]};
+                __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));
+            } else if constexpr (N == 4) {
+                const u2 t = {w[0], w[1]};
+                __builtin_nontemporal_store(t, reinterpret_cast<u2 *>(p));
+            } else {
+                *reinterpret_cast<uint32_t *>(p) = w[0];
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < N; ++i) p[i] = bf16_bits(v[i]);
         }
     }
 }
-
 
 }  // namespace bs

@@ -63,7 +63,7 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
             const void *rp = res[arg];
             Raw<BF16, VEC> rr[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) rr[u] = load_raw<BF16, VEC>(rp, off[u]);
+            for (int u = 0; u < U; ++u) rr[u] = load_raw<BF16, VEC, true>(rp, off[u]);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float r[VEC];
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
         valid[u] = i < k.total;
         i = valid[u] ? i : 0u;
         off[u] = i * VEC;
-        raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
+        raw[u] = load_raw<BF16, VEC, true>(k.in, off[u]);
         const uint32_t plane = fdiv(i, k.div_plane);
         c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
     }
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
         in_off[u] = plane * (uint32_t)(k.H * k.W) + idx0[u];
         out_off[u] = (plane * (uint32_t)k.Ho + oh) * (uint32_t)k.Wo + cv * NO;
 #pragma unroll
-        for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<BF16, VEC>(k.in, in_off[u] + dh * (uint32_t)k.W);
+        for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<BF16, VEC, true>(k.in, in_off[u] + dh * (uint32_t)k.W);
     }
 
     float y[U][NO];

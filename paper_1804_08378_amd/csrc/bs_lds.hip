@@ -320,7 +320,7 @@ BS_DEV void phase0(const LdsSeqK &k, const TileCtx &t, float *lds, int32_t r0, i
                     const int32_t gr = r0 + r;
                     inimg[u] = col_in && r < lv.rows && gr >= 0 && gr < lv.H;
                     off[u] = inimg[u] ? gplane + (uint32_t)gr * (uint32_t)lv.W + (uint32_t)gc : 0u;
-                    raw[u] = load_raw<BF16, VEC>(k.in, off[u]);
+                    raw[u] = load_raw<BF16, VEC, true>(k.in, off[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {

@@ -10,8 +10,9 @@
 // one 128-bit vector each, plus the pw columns to the left and kw - sw - pw columns to the
 // right of its block as scalar loads that hit the lines its neighbours fetch.  Cells outside
 // the plane are the pooling operation's padding (-inf / +0) and are never computed from
-// earlier layers.  Loads for the next output row are issued before the current one is
-// reduced.  Only the rows shared by two vertically adjacent chunks are read twice.
+// earlier layers.  A lane handles OR output rows per iteration and issues the loads for the
+// next iteration before it reduces the current one.  Only the rows shared by two vertically
+// adjacent chunks are read twice.
 //
 // The pooling shape and the element-wise lists are template arguments; the planner uses this
 // kernel only for the signatures instantiated in the table at the end (rows_supported()).
@@ -27,6 +28,7 @@ struct RowsSpec {
 };
 
 // element-wise list codes (base 4 digits, first operation lowest): see rows_ew_code()
+constexpr int K_ROWS_OR = 1;  // output rows per lane per iteration
 constexpr int RW_NONE = 0;
 constexpr int RW_BN_RELU = OP_BN + 4 * OP_RELU;
 
@@ -84,7 +86,7 @@ BS_DEV void rows_apply(float (&x)[N], const RowsParams<EW> &p)
     }
 }
 
-template <bool BF16, int VEC, class P, int EWPRE, int EWPOST, bool WANT_IDX>
+template <bool BF16, int VEC, class P, int EWPRE, int EWPOST, bool WANT_IDX, int OR>
 __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
 {
     constexpr int KH = P::kh, KW = P::kw, SH = P::sh, SW = P::sw, PH = P::ph, PW = P::pw;
@@ -92,7 +94,9 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
     constexpr int NL = PW;                 // columns left of the block
     constexpr int NX = KW - SW - PW;       // columns right of the block
     constexpr int NC = NL + VEC + NX;      // columns the VO windows span
-    constexpr int NS = SH < KH ? SH : KH;  // new input rows per output row
+    constexpr int WR = KH + (OR - 1) * SH;  // input rows of OR consecutive output rows
+    constexpr int ST = OR * SH;             // rows the window slides per iteration
+    constexpr int NS = ST < WR ? ST : WR;   // new input rows per iteration
     constexpr int ES = BF16 ? 2 : 4;
     constexpr bool IS_MAX = P::kind == OP_MAXPOOL;
     static_assert(VEC % SW == 0 && NX >= 0 && NL >= 0, "unsupported pooling shape");
@@ -100,6 +104,7 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
     using EWQ = RowsEw<EWPOST>;
     const float padv = IS_MAX ? -INFINITY : 0.0f;
 
+    // lane -> (plane, chunk, column block j), column block fastest
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     const bool live = i < k.total;
     i = live ? i : 0u;
@@ -170,88 +175,95 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
     const bool vec_store = (k.Wo % VO) == 0 && ow0 + VO <= k.Wo;
     const uint32_t oplane = plane * (uint32_t)(k.Ho * k.Wo);
 
-    float win[KH][NC];
+    // the window holds the input rows of OR consecutive output rows
+    float win[WR][NC];
     {
-        RowRaw r[KH];
+        RowRaw r[WR];
 #pragma unroll
-        for (int dh = 0; dh < KH; ++dh) fetch(oh0 * SH - PH + dh, r[dh]);
+        for (int w = 0; w < WR; ++w) fetch(oh0 * SH - PH + w, r[w]);
 #pragma unroll
-        for (int dh = 0; dh < KH; ++dh) settle(r[dh], win[dh]);
+        for (int w = 0; w < WR; ++w) settle(r[w], win[w]);
     }
-    for (int32_t oh = oh0; oh < oh1; ++oh) {
+    for (int32_t oh = oh0; oh < oh1; oh += OR) {
         const int32_t h0 = oh * SH - PH;
-        // loads for the next output row first
+        // loads for the next OR output rows first
         RowRaw nr[NS];
 #pragma unroll
-        for (int n = 0; n < NS; ++n) fetch(oh + 1 < oh1 ? h0 + SH + (KH - NS) + n : -1, nr[n]);
+        for (int n = 0; n < NS; ++n) fetch(oh + OR < oh1 ? h0 + ST + (WR - NS) + n : -1, nr[n]);
 
-        float y[VO];
-        int32_t yi[VO];
 #pragma unroll
-        for (int e = 0; e < VO; ++e) {
-            const int32_t w0 = col0 - PW + e * SW;
-            if (IS_MAX) {
-                float best = -INFINITY;
-                int32_t bi = max(h0, 0) * k.W + max(w0, 0);  // first in-range cell
+        for (int o = 0; o < OR; ++o) {
+            float y[VO];
+            int32_t yi[VO];
+            const int32_t hw = h0 + o * SH;  // first input row of this output row's windows
 #pragma unroll
-                for (int dh = 0; dh < KH; ++dh)
+            for (int e = 0; e < VO; ++e) {
+                const int32_t w0 = col0 - PW + e * SW;
+                if (IS_MAX) {
+                    float best = -INFINITY;
+                    int32_t bi = max(hw, 0) * k.W + max(w0, 0);  // first in-range cell
 #pragma unroll
-                    for (int dw = 0; dw < KW; ++dw) {
-                        const float v = win[dh][e * SW + dw];
-                        if constexpr (WANT_IDX) {
-                            const bool g = v > best;
-                            best = g ? v : best;
-                            bi = g ? (h0 + dh) * k.W + w0 + dw : bi;
-                        } else {
-                            best = __builtin_fmaxf(best, v);
+                    for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                        for (int dw = 0; dw < KW; ++dw) {
+                            const float v = win[o * SH + dh][e * SW + dw];
+                            if constexpr (WANT_IDX) {
+                                const bool g = v > best;
+                                best = g ? v : best;
+                                bi = g ? (hw + dh) * k.W + w0 + dw : bi;
+                            } else {
+                                best = __builtin_fmaxf(best, v);
+                            }
+                        }
+                    y[e] = best;
+                    yi[e] = bi;
+                } else {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                        for (int dw = 0; dw < KW; ++dw) sum = sum + win[o * SH + dh][e * SW + dw];
+                    float inv = k.pool.inv_kk;
+                    if (!k.pool.count_include_pad) {
+                        const int32_t nr_ = min(hw + KH, k.H) - max(hw, 0);
+                        const int32_t nc_ = min(w0 + KW, k.W) - max(w0, 0);
+                        inv = 1.0f / (float)max(nr_ * nc_, 1);
+                    }
+                    y[e] = round_store<BF16>(sum * inv);
+                    yi[e] = 0;
+                }
+            }
+            rows_apply<BF16, EWQ, VO>(y, qp);
+            if (oh + o < oh1) {
+                const uint32_t ooff = oplane + (uint32_t)((oh + o) * k.Wo + ow0);
+                if (vec_store) {
+                    store_elems<BF16, VO>(k.out, ooff, y);
+                    if constexpr (WANT_IDX) {
+                        if (k.idx) {
+#pragma unroll
+                            for (int e = 0; e < VO; ++e) k.idx[ooff + e] = yi[e];
                         }
                     }
-                y[e] = best;
-                yi[e] = bi;
-            } else {
-                float sum = 0.0f;
+                } else {
 #pragma unroll
-                for (int dh = 0; dh < KH; ++dh)
-#pragma unroll
-                    for (int dw = 0; dw < KW; ++dw) sum = sum + win[dh][e * SW + dw];
-                float inv = k.pool.inv_kk;
-                if (!k.pool.count_include_pad) {
-                    const int32_t nr_ = min(h0 + KH, k.H) - max(h0, 0);
-                    const int32_t nc_ = min(w0 + KW, k.W) - max(w0, 0);
-                    inv = 1.0f / (float)max(nr_ * nc_, 1);
-                }
-                y[e] = round_store<BF16>(sum * inv);
-                yi[e] = 0;
-            }
-        }
-        rows_apply<BF16, EWQ, VO>(y, qp);
-        const uint32_t ooff = oplane + (uint32_t)(oh * k.Wo + ow0);
-        if (vec_store) {
-            store_elems<BF16, VO>(k.out, ooff, y);
-            if constexpr (WANT_IDX) {
-                if (k.idx) {
-#pragma unroll
-                    for (int e = 0; e < VO; ++e) k.idx[ooff + e] = yi[e];
+                    for (int e = 0; e < VO; ++e)
+                        if (ow0 + e < k.Wo) {
+                            const float one[1] = {y[e]};
+                            store_elems<BF16, 1>(k.out, ooff + e, one);
+                            if constexpr (WANT_IDX) {
+                                if (k.idx) k.idx[ooff + e] = yi[e];
+                            }
+                        }
                 }
             }
-        } else {
-#pragma unroll
-            for (int e = 0; e < VO; ++e)
-                if (ow0 + e < k.Wo) {
-                    const float one[1] = {y[e]};
-                    store_elems<BF16, 1>(k.out, ooff + e, one);
-                    if constexpr (WANT_IDX) {
-                        if (k.idx) k.idx[ooff + e] = yi[e];
-                    }
-                }
         }
-        // slide the window down by sh rows
+        // slide the window down by OR * sh rows
 #pragma unroll
-        for (int dh = 0; dh + SH < KH; ++dh)
+        for (int w = 0; w + ST < WR; ++w)
 #pragma unroll
-            for (int n = 0; n < NC; ++n) win[dh][n] = win[dh + SH][n];
+            for (int n = 0; n < NC; ++n) win[w][n] = win[w + ST][n];
 #pragma unroll
-        for (int n = 0; n < NS; ++n) settle(nr[n], win[KH - NS + n]);
+        for (int n = 0; n < NS; ++n) settle(nr[n], win[WR - NS + n]);
     }
 }
 
@@ -314,8 +326,8 @@ static bool rows_launch_t(const PoolRowsK &k, bool want_idx, dim3 grid, dim3 blo
         using P = decltype(spec);
         constexpr int PC = decltype(pc)::value, QC = decltype(qc)::value;
         if (!rows_pool_is<P>(k.pool) || cp != PC || cq != QC) return false;
-        if (want_idx) pool_rows_kernel<BF16, VEC, P, PC, QC, true><<<grid, block, 0, st>>>(k);
-        else pool_rows_kernel<BF16, VEC, P, PC, QC, false><<<grid, block, 0, st>>>(k);
+        if (want_idx) pool_rows_kernel<BF16, VEC, P, PC, QC, true, K_ROWS_OR><<<grid, block, 0, st>>>(k);
+        else pool_rows_kernel<BF16, VEC, P, PC, QC, false, K_ROWS_OR><<<grid, block, 0, st>>>(k);
         return true;
     });
 }
