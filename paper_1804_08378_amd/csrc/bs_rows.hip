@@ -188,8 +188,11 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
         const int32_t h0 = oh * SH - PH;
         // loads for the next OR output rows first
         RowRaw nr[NS];
+        const bool more = oh + OR < oh1;
+        if (more) {
 #pragma unroll
-        for (int n = 0; n < NS; ++n) fetch(oh + OR < oh1 ? h0 + ST + (WR - NS) + n : -1, nr[n]);
+            for (int n = 0; n < NS; ++n) fetch(h0 + ST + (WR - NS) + n, nr[n]);
+        }
 
 #pragma unroll
         for (int o = 0; o < OR; ++o) {
@@ -262,8 +265,10 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
         for (int w = 0; w + ST < WR; ++w)
 #pragma unroll
             for (int n = 0; n < NC; ++n) win[w][n] = win[w + ST][n];
+        if (more) {
 #pragma unroll
-        for (int n = 0; n < NS; ++n) settle(nr[n], win[WR - NS + n]);
+            for (int n = 0; n < NS; ++n) settle(nr[n], win[WR - NS + n]);
+        }
     }
 }
 

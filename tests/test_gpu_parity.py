@@ -264,3 +264,33 @@ def test_pool_rows_kernel(shape, dtype):
         # the same stack through the LDS kernels agrees as well
         info = check(layers, x, [], dtype, f"rows/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
         assert info["sequences"][0]["variant_name"] == "lds_tile"
+
+
+# ------------------------------------------------------------------ special values
+def test_signed_zero_and_subnormals_follow_the_oracle():
+    """ReLU maps -0 to +0, subnormal values pass through unchanged, and max pooling of windows
+    that mix +0 and -0 returns a zero (sign not compared) with the oracle's argmax."""
+    vals = np.array([-0.0, 0.0, -1.0, 1e-40, -1e-40, 2.5, 1e-38, -3.0], np.float32)
+    x = np.tile(vals, 64 * 4).reshape(1, 4, 16, 32).copy()
+    ref, _, _ = bf.run_stack([wl.relu()], x)
+    out, _, _ = run_gpu([wl.relu()], x, [], "f32")
+    assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
+    for layers in ([wl.relu(), wl.maxpool(2, 2, 0, True)], [wl.relu(), wl.maxpool(3, 2, 1, True)],
+                   [wl.relu(), wl.maxpool(3, 2, 1, False)], [wl.relu(), wl.avgpool(3, 1, 1)]):
+        ref, ridx, _ = bf.run_stack(layers, x)
+        out, idx, _ = run_gpu(layers, x, [], "f32")
+        assert np.array_equal(out.view(np.uint32), ref.view(np.uint32)), layers
+        for a, b in zip(idx, ridx):
+            assert np.array_equal(a, b)
+    # windows holding only zeros of both signs: values compare equal; indices follow the
+    # first-maximum rule of the oracle when they are requested
+    z = np.zeros((1, 2, 8, 8), np.float32)
+    z[:, :, ::2, ::2] = -0.0
+    for want in (True, False):
+        layers = [wl.maxpool(2, 2, 0, want)]
+        ref, ridx, _ = bf.run_stack(layers, z)
+        out, idx, _ = run_gpu(layers, z, [], "f32")
+        assert np.array_equal(out, ref)
+        if want:
+            assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
+            assert np.array_equal(idx[0], ridx[0])
