@@ -43,7 +43,7 @@ def test_step_rule_elementwise_always_joins_second_pool_opens_a_step():
 
 @pytest.mark.parametrize("name,steps,variant", [
     ("tiny", 1, "pool_direct"), ("vgg_a", 1, "pool_direct"), ("vgg_b", 1, "pool_direct"),
-    ("vgg_c", 1, "pool_direct"), ("resnet_stem", 1, "lds_tile"), ("resnet_tail", 1, "stream"),
+    ("vgg_c", 1, "pool_direct"), ("resnet_stem", 1, "pool_rows"), ("resnet_tail", 1, "stream"),
     ("densenet_dense", 1, "stream"), ("densenet_trans", 1, "pool_direct"), ("halo_stress", 2, "lds_tile"),
 ])
 def test_baseline_configs_are_one_fused_sequence(name, steps, variant):
