@@ -565,6 +565,46 @@ __global__ __launch_bounds__(512) void lds_sig_kernel(const LdsSeqK k)
 }
 
 // =============================================================================
+// Repeated build: every level has the same pooling shape and element-wise list (the
+// blocks of Section 5.1 stacked L deep); L is read at run time, the phase code is the
+// signature build's.  The first phase reads the level-0 rows, whose rectangle starts
+// delta0 & 3 floats into an aligned vector: one instance per value.
+// =============================================================================
+template <bool BF16, int VEC, bool WANT_IDX, int EW0, class LV>
+__global__ __launch_bounds__(512) void lds_rep_kernel(const LdsSeqK k)
+{
+    extern __shared__ __align__(16) float lds[];
+    using P = typename LV::P;
+    using EW = typename LV::EW;
+    const int32_t L = k.n_levels;
+    const TileCtx t = tile_ctx(k);
+    {
+        int32_t r0 = t.ti * k.TH, c0 = t.tj * k.TW;
+        for (int32_t l = L; l >= 1; --l) origin_step(k.pool[l], r0, c0);
+        phase0<BF16, VEC, EwList<EW0>>(k, t, lds, r0, c0, pad_value(P(k.pool[1])));
+    }
+    __syncthreads();
+    for (int32_t l = 1; l <= L; ++l) {
+        const PhaseCtx cx = phase_ctx(k, t, lds, l);
+        const P p(k.pool[l]);
+        const LevelK &lv = k.level[l], &pv = k.level[l - 1];
+        const int32_t d = cx.d_lo & 3;
+        if (cx.last) {
+            if (d == 0) pool_phase<BF16, P, EW, 0, WANT_IDX, true>(k, t, lv, pv, p, cx);
+            else if (d == 1) pool_phase<BF16, P, EW, 1, WANT_IDX, true>(k, t, lv, pv, p, cx);
+            else if (d == 2) pool_phase<BF16, P, EW, 2, WANT_IDX, true>(k, t, lv, pv, p, cx);
+            else pool_phase<BF16, P, EW, 3, WANT_IDX, true>(k, t, lv, pv, p, cx);
+        } else {
+            if (d == 0) pool_phase<BF16, P, EW, 0, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            else if (d == 1) pool_phase<BF16, P, EW, 1, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            else if (d == 2) pool_phase<BF16, P, EW, 2, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            else pool_phase<BF16, P, EW, 3, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            __syncthreads();
+        }
+    }
+}
+
+// =============================================================================
 // Signature table and launcher.
 // =============================================================================
 using Max3s2p1 = PoolSpec<OP_MAXPOOL, 3, 3, 2, 2, 1, 1, 1>;
@@ -609,6 +649,17 @@ static bool try_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size
     return true;
 }
 
+template <bool BF16, int VEC, int EW0, class LV>
+static bool try_rep(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st)
+{
+    if (k.n_levels < 3 || k.vec != VEC || ew_code(k.level[0]) != EW0) return false;
+    for (int l = 1; l <= k.n_levels; ++l)
+        if (!pool_is<typename LV::P>(k.pool[l]) || ew_code(k.level[l]) != LV::EW::code) return false;
+    if (want_idx) lds_rep_kernel<BF16, VEC, true, EW0, LV><<<grid, block, lds, st>>>(k);
+    else lds_rep_kernel<BF16, VEC, false, EW0, LV><<<grid, block, lds, st>>>(k);
+    return true;
+}
+
 // Stack signatures with a dedicated build.  First match wins; anything else runs the
 // run-time build.
 template <bool BF16, int VEC>
@@ -624,6 +675,8 @@ static bool launch_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, s
     if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, NoLvl>(k, want_idx, grid, block, lds, st)) return true;
     if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st)) return true;
     if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st)) return true;
+    // three or more of those blocks in one sequence
+    if (try_rep<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st)) return true;
     return false;
 }
 
