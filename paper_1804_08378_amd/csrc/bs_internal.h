@@ -264,6 +264,7 @@ void set_hip_error(int32_t e);
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);
 bs_status launch_rows(const PoolRowsK &k, bool bf16, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
+bool lds_fast_path(const LdsSeqK &k);
 bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
 
 }  // namespace bs

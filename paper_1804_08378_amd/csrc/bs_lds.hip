@@ -634,15 +634,16 @@ static bool pool_is(const PoolK &q)
 }
 
 template <bool BF16, int VEC, int EW0, class L1, class L2>
-static bool try_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st)
+static bool try_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st, bool dry)
 {
     constexpr bool TWO = !std::is_same<L2, NoLvl>::value;
-    if (k.n_levels != (TWO ? 2 : 1) || k.vec != VEC) return false;
+    if (k.n_levels != (TWO ? 2 : 1) || (!dry && k.vec != VEC)) return false;
     if (ew_code(k.level[0]) != EW0) return false;
     if (!pool_is<typename L1::P>(k.pool[1]) || ew_code(k.level[1]) != L1::EW::code) return false;
     if constexpr (TWO) {
         if (!pool_is<typename L2::P>(k.pool[2]) || ew_code(k.level[2]) != L2::EW::code) return false;
     }
+    if (dry) return true;
     if (k.delta0 != sig_delta0<VEC, L1, L2>()) return false;
     if (want_idx) lds_sig_kernel<BF16, VEC, true, EW0, L1, L2><<<grid, block, lds, st>>>(k);
     else lds_sig_kernel<BF16, VEC, false, EW0, L1, L2><<<grid, block, lds, st>>>(k);
@@ -650,11 +651,12 @@ static bool try_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size
 }
 
 template <bool BF16, int VEC, int EW0, class LV>
-static bool try_rep(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st)
+static bool try_rep(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st, bool dry)
 {
-    if (k.n_levels < 3 || k.vec != VEC || ew_code(k.level[0]) != EW0) return false;
+    if (k.n_levels < 3 || (!dry && k.vec != VEC) || ew_code(k.level[0]) != EW0) return false;
     for (int l = 1; l <= k.n_levels; ++l)
         if (!pool_is<typename LV::P>(k.pool[l]) || ew_code(k.level[l]) != LV::EW::code) return false;
+    if (dry) return true;
     if (want_idx) lds_rep_kernel<BF16, VEC, true, EW0, LV><<<grid, block, lds, st>>>(k);
     else lds_rep_kernel<BF16, VEC, false, EW0, LV><<<grid, block, lds, st>>>(k);
     return true;
@@ -663,21 +665,29 @@ static bool try_rep(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size
 // Stack signatures with a dedicated build.  First match wins; anything else runs the
 // run-time build.
 template <bool BF16, int VEC>
-static bool launch_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st)
+static bool launch_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st, bool dry)
 {
     // BN -> ReLU -> MaxPool 3/2/1 (ResNet stem), and the pool on its own (layer by layer)
-    if (try_sig<BF16, VEC, EW_BN_RELU, Lvl<Max3s2p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s2p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st)) return true;
+    if (try_sig<BF16, VEC, EW_BN_RELU, Lvl<Max3s2p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s2p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st, dry)) return true;
     // BN -> ReLU -> AvgPool 3/1/1 -> MaxPool 3/2/1 -> BN -> ReLU (halo stress), and its average alone
-    if (try_sig<BF16, VEC, EW_BN_RELU, Lvl<Avg3s1p1, EW_NONE>, Lvl<Max3s2p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Avg3s1p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st)) return true;
+    if (try_sig<BF16, VEC, EW_BN_RELU, Lvl<Avg3s1p1, EW_NONE>, Lvl<Max3s2p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<BF16, VEC, EW_NONE, Lvl<Avg3s1p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st, dry)) return true;
     // <MaxPool 3/1/1, BN, ReLU> blocks of Section 5.1: one and two per sequence, and the pool alone
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, NoLvl>(k, want_idx, grid, block, lds, st)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st)) return true;
+    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, NoLvl>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_NONE>, NoLvl>(k, want_idx, grid, block, lds, st, dry)) return true;
     // three or more of those blocks in one sequence
-    if (try_rep<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st)) return true;
+    if (try_rep<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
     return false;
+}
+
+// Is there a signature / repeated build for this sequence shape (pooling operations and
+// element-wise lists only; tile geometry is not looked at)?  The planner uses it to avoid
+// merging steps into a sequence that would fall back to the much slower run-time build.
+bool lds_fast_path(const LdsSeqK &k)
+{
+    return launch_sig<false, 4>(k, false, dim3(1), dim3(64), 0, nullptr, true);
 }
 
 bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid_n, int32_t threads, uint64_t lds_bytes, void *stream)
@@ -690,13 +700,13 @@ bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid_n, int32_t thread
         if (k.pool[l].idx_slot >= 0 && k.idx[k.pool[l].idx_slot]) want_idx = true;
     if (bf16) {
         if (k.vec == 8) {
-            if (!launch_sig<true, 8>(k, want_idx, grid, block, lds, st)) lds_tile_kernel<true, 8><<<grid, block, lds, st>>>(k);
+            if (!launch_sig<true, 8>(k, want_idx, grid, block, lds, st, false)) lds_tile_kernel<true, 8><<<grid, block, lds, st>>>(k);
         } else {
             lds_tile_kernel<true, 1><<<grid, block, lds, st>>>(k);
         }
     } else {
         if (k.vec == 4) {
-            if (!launch_sig<false, 4>(k, want_idx, grid, block, lds, st)) lds_tile_kernel<false, 4><<<grid, block, lds, st>>>(k);
+            if (!launch_sig<false, 4>(k, want_idx, grid, block, lds, st, false)) lds_tile_kernel<false, 4><<<grid, block, lds, st>>>(k);
         } else {
             lds_tile_kernel<false, 1><<<grid, block, lds, st>>>(k);
         }

@@ -492,6 +492,30 @@ static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, 
     q.redundancy = rows_loaded / (double)k.H;
 }
 
+// Does a pre-compiled fast kernel exist for this op range?  Streaming, disjoint-window and
+// rows sequences always have one; an LDS sequence only if its signature is instantiated.
+static bool seq_is_fast(const bs_stack *s, int32_t first_op, int32_t n_ops)
+{
+    if (count_pools(s, first_op, n_ops) == 0) return true;
+    if (direct_applicable(s, first_op, n_ops) || rows_applicable(s, first_op, n_ops, nullptr)) return true;
+    if (!seq_capacity_ok(s, first_op, n_ops, false)) return false;
+    Sequence tmp;
+    LdsSeqK k{};
+    int level = 0;
+    for (int32_t i = first_op; i < first_op + n_ops; ++i) {
+        const Op &op = s->ops[i];
+        if (!op_is_elementwise(op.kind)) {
+            k.pool[++level] = make_pool(op, nullptr, tmp);
+            tmp.n_idx = 0;
+        } else if (op.kind != OP_AVGNORM) {
+            LevelK &lv = k.level[level];
+            fill_ew(s, op, tmp, lv.ew[lv.n_ew++]);
+        }
+    }
+    k.n_levels = level;
+    return lds_fast_path(k);
+}
+
 static bool audit_lds(const Sequence &q);
 
 static bs_status plan_lds(const bs_stack *s, Sequence &q, const bs_plan_options &o, const Limits &lim)
@@ -714,6 +738,13 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             if (fits && o.max_steps_per_sequence > 0 && trial.n_steps > o.max_steps_per_sequence) fits = false;
             if (fits && !seq_capacity_ok(s, fo, no, true)) fits = false;
             if (fits && seq_min_lds(s, fo, no, threads) > lim.max_lds_bytes) fits = false;
+            // cost rule: do not trade a sequence that has a pre-compiled fast kernel for a longer
+            // one that would run the much slower run-time-shape build
+            if (fits && o.force_variant == BS_VARIANT_AUTO) {
+                int32_t co, cn;
+                range_ops(cur, co, cn);
+                if (seq_is_fast(s, co, cn) && !seq_is_fast(s, fo, no)) fits = false;
+            }
             if (fits) {
                 cur = trial;
             } else {

@@ -26,7 +26,12 @@ def test_listing2_example_partition():
     assert info["operations"] == ["MaxPooling", "BatchNorm", "ReLU", "AvgPooling", "AvgNormalization"]
     assert steps_of(info) == [(0, 3), (3, 2)]
     assert [s["pool_operation"] for s in info["steps"]] == [0, 3]
-    assert info["n_sequences"] == 1 and info["workspace_bytes"] == 0
+    # both steps fit one sequence (Listing 2's sequence_0); the automatic plan keeps them apart
+    # only because the first step alone has a pre-compiled fast kernel and the pair has none
+    one = plan(layers, (1, 4, 16, 16), force_variant=bs.BS_VARIANT_LDS_TILE)
+    assert one["n_sequences"] == 1 and one["workspace_bytes"] == 0
+    assert steps_of(one) == [(0, 3), (3, 2)]
+    assert info["n_sequences"] == 2 and info["workspace_bytes"] > 0
 
 
 def test_step_rule_elementwise_always_joins_second_pool_opens_a_step():
