@@ -155,6 +155,50 @@ def cpu_baseline(names, dtype, batch, passes):
                       "single-thread pass; same algorithmic-bytes metric"}
 
 
+def deep_stacks(shape=(64, 64, 56, 56), counts=(1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 40)):
+    """Section 5.1: networks of n blocks <MaxPool k3 s1 p1, BatchNorm, ReLU>, executed layer by
+    layer and fused with at most 1 step, at most 5 steps, and unrestricted steps per sequence.
+    The paper does not state its tensor shape; 64x64x56x56 fp32 is this benchmark's choice.
+    Times are the minimum of 10 launches (the paper's protocol) over rotating inputs."""
+    import torch
+    from paper_1804_08378_amd import brainslug as bs
+    from paper_1804_08378_amd import workloads as wl
+
+    xs = [torch.from_numpy(wl.activation(shape, 0)).cuda()]
+    xs += [xs[0].clone() for _ in range(9)]
+    strategies = (("layer_by_layer", dict(breadth_first=1)), ("steps1", dict(max_steps_per_sequence=1)),
+                  ("steps5", dict(max_steps_per_sequence=5)), ("unrestricted", dict()))
+    rows = []
+    log(f"{'blocks':>6}" + "".join(f"{n + ' us (seq)':>24}" for n, _ in strategies) + f"{'best speed-up':>15}")
+    for n in counts:
+        layers = sum(([wl.maxpool(3, 1, 1), wl.bn_params(shape[1], 100 + i), wl.relu()] for i in range(n)), [])
+        row = {"blocks": n}
+        for name, opts in strategies:
+            st = bs.Stack(layers, shape, "f32").plan(**opts)
+            outs = [st.alloc_outputs("cuda", False)[0] for _ in range(10)]
+            st.workspace("cuda")
+            for i in range(3):
+                st.run(xs[i], out=outs[i], indices=[])
+            torch.cuda.synchronize()
+            times = []
+            for i in range(10):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                st.run(xs[i], out=outs[i], indices=[])
+                b.record()
+                torch.cuda.synchronize()
+                times.append(a.elapsed_time(b) * 1e3)
+            row[name] = {"us_min": round(min(times), 1), "sequences": st.info()["n_sequences"]}
+            st.close()
+            del outs
+        row["speedup_best_fused_vs_layer_by_layer"] = round(
+            row["layer_by_layer"]["us_min"] / min(row[k]["us_min"] for k in ("steps1", "steps5", "unrestricted")), 2)
+        rows.append(row)
+        log(f"{n:>6}" + "".join(f"{row[k]['us_min']:>17.1f} ({row[k]['sequences']:>3})" for k, _ in strategies)
+            + f"{row['speedup_best_fused_vs_layer_by_layer']:>15.2f}")
+    return {"shape": list(shape), "dtype": "f32", "protocol": "min of 10 launches", "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -167,6 +211,9 @@ def main():
     ap.add_argument("--no-baseline", action="store_true",
                     help="skip the layer-by-layer HIP plan (its pooling layer runs the same kernel symbol "
                          "as the fused stack, which would mix the two in a rocprofv3 --stats summary)")
+    ap.add_argument("--deep", action="store_true",
+                    help="also run the stacked-layers experiment of Section 5.1: 1..40 blocks of "
+                         "<MaxPool 3/1/1, BatchNorm, ReLU> under the three sequence strategies")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
                     help="counter probe for rocprofv3 --pmc: N launches of a plain copy of known size, "
                          "then N launches of each VGG stack; no timing, no JSON")
@@ -248,6 +295,9 @@ def main():
         out["cpu_baseline"] = cpu_baseline(wl.VGG_STACKS, "f32", args.cpu_batch, args.cpu_passes)
     else:
         out["cpu_baseline"] = None
+
+    if args.deep:
+        out["deep_stacks"] = deep_stacks()
 
     if args.all:
         del stacks

@@ -30,6 +30,7 @@ struct RowsSpec {
 // element-wise list codes (base 4 digits, first operation lowest): see rows_ew_code()
 constexpr int K_ROWS_OR = 1;  // output rows per lane per iteration
 constexpr int RW_NONE = 0;
+constexpr int RW_RELU = OP_RELU;
 constexpr int RW_BN_RELU = OP_BN + 4 * OP_RELU;
 
 template <int CODE>
@@ -306,6 +307,8 @@ static bool rows_for_each_signature(F &&f)
            f(RMax3s2p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
            f(RMax3s2p0{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
            f(RMax3s2p0{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RMax3s2p0{}, std::integral_constant<int, RW_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
+           f(RMax3s2p1{}, std::integral_constant<int, RW_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
            f(RMax3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_BN_RELU>{}) ||
            f(RMax3s1p1{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
            f(RMax3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||

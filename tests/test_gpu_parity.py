@@ -243,6 +243,8 @@ def _rows_stacks(c):
         "max3s2p1": [wl.maxpool(3, 2, 1, True)],
         "stem_nopad": [wl.bn_params(c, 61), wl.relu(), wl.maxpool(3, 2, 0, True)],
         "max3s2p0": [wl.maxpool(3, 2, 0, False)],
+        "relu_max3s2p0": [wl.relu(), wl.maxpool(3, 2, 0, True)],
+        "relu_max3s2p1": [wl.relu(), wl.maxpool(3, 2, 1, False)],
         "block": [wl.maxpool(3, 1, 1, True), wl.bn_params(c, 62), wl.relu()],
         "bn_relu_max3s1": [wl.bn_params(c, 63), wl.relu(), wl.maxpool(3, 1, 1, False)],
         "max3s1p1": [wl.maxpool(3, 1, 1, True)],
