@@ -50,7 +50,7 @@ constexpr int K_MAX_STREAM_EW = 16;
 constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
 constexpr int K_STREAM_U = 4;     // 128-bit vectors per lane in stream_kernel
-constexpr int K_DIRECT_U = 2;     // units per lane in pool_direct_kernel
+constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
 
 // n / d for 0 <= n < 2^31 by multiply-high and shift.
 struct FastDiv {

@@ -114,7 +114,11 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
 // produces VEC / KW outputs.  Consecutive lanes take consecutive column blocks, so each
 // row load of a wave is one contiguous run.
 // =============================================================================
-template <bool BF16, int VEC, int KH, int KW, int U>
+// SIG selects how the element-wise lists are executed: 0 interprets k.pre / k.post at
+// run time; 1 is compiled for "BatchNorm, ReLU, pool" with nothing after the pool (the
+// VGG stack, the DenseNet transition), whose BatchNorm parameters are requested together
+// with the data so a wave makes one round trip to memory instead of two.
+template <bool BF16, int VEC, int KH, int KW, int U, int SIG>
 __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 {
     constexpr int NO = VEC / KW;  // outputs per unit
@@ -142,6 +146,15 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 #pragma unroll
         for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<BF16, VEC, true>(k.in, in_off[u] + dh * (uint32_t)k.W);
     }
+    float sc[U], sh[U];
+    if constexpr (SIG == 1) {
+        const int32_t arg = k.pre[0].arg;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            sc[u] = k.params[arg + c[u]];
+            sh[u] = k.params[arg + k.C + c[u]];
+        }
+    }
 
     float y[U][NO];
     int32_t yi[U][NO];
@@ -158,7 +171,15 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
             o1[dh] = in_off[u] + dh * (uint32_t)k.W;
             unpack<BF16, VEC>(raw[u][dh], x[dh]);
         }
-        apply_ew<BF16, VEC, KH>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
+        if constexpr (SIG == 1) {
+#pragma unroll
+            for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)
+                    x[dh][i] = __builtin_fmaxf(round_store<BF16>(__builtin_fmaf(x[dh][i], sc[u], sh[u])), 0.0f);
+        } else {
+            apply_ew<BF16, VEC, KH>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
+        }
         if (is_max) {
             if (want_idx) {
 #pragma unroll
@@ -204,7 +225,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
             }
         }
     }
-    apply_ew<BF16, NO, U>(y, c, out_off, k.post, k.n_post, k.params, k.C, k.res);
+    if constexpr (SIG == 0) apply_ew<BF16, NO, U>(y, c, out_off, k.post, k.n_post, k.params, k.C, k.res);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (!valid[u]) continue;
@@ -278,11 +299,15 @@ template <bool BF16, int VEC, int KH>
 static void launch_direct_kw(const PoolDirectK &k, int kw, dim3 grid, dim3 block, hipStream_t st)
 {
     if constexpr (VEC == 8) {
-        if (kw == 8) { pool_direct_kernel<BF16, VEC, KH, 8, K_DIRECT_U><<<grid, block, 0, st>>>(k); return; }
+        if (kw == 8) { pool_direct_kernel<BF16, VEC, KH, 8, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k); return; }
     }
-    if (kw == 1) pool_direct_kernel<BF16, VEC, KH, 1, K_DIRECT_U><<<grid, block, 0, st>>>(k);
-    else if (kw == 2) pool_direct_kernel<BF16, VEC, KH, 2, K_DIRECT_U><<<grid, block, 0, st>>>(k);
-    else pool_direct_kernel<BF16, VEC, KH, 4, K_DIRECT_U><<<grid, block, 0, st>>>(k);
+    if constexpr (KH == 2) {
+        const bool bn_relu_pool = k.n_pre == 2 && k.pre[0].kind == OP_BN && k.pre[1].kind == OP_RELU && k.n_post == 0;
+        if (kw == 2 && bn_relu_pool) { pool_direct_kernel<BF16, VEC, 2, 2, K_DIRECT_U, 1><<<grid, block, 0, st>>>(k); return; }
+    }
+    if (kw == 1) pool_direct_kernel<BF16, VEC, KH, 1, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
+    else if (kw == 2) pool_direct_kernel<BF16, VEC, KH, 2, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
+    else pool_direct_kernel<BF16, VEC, KH, 4, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
 }
 
 template <bool BF16, int VEC>
