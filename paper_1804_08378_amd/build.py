@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbrainslug_hip.so")
-SOURCES = ["bs_stack.cpp", "bs_plan.cpp", "bs_run.cpp", "bs_kernels.hip", "bs_lds.hip", "bs_rows.hip"]
+SOURCES = ["bs_stack.cpp", "bs_plan.cpp", "bs_run.cpp", "bs_kernels.hip", "bs_lds.hip", "bs_rows.hip", "bs_rows2.hip"]
 
 # -ffp-contract=off: the only fused multiply-add is the explicit one of BatchNorm.
 # packed-fp32 instructions are disabled for the device code.

@@ -50,6 +50,7 @@ constexpr int K_MAX_STREAM_EW = 16;
 constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
 constexpr int K_STREAM_U = 4;     // 128-bit vectors per lane in stream_kernel
+constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
 
 // n / d for 0 <= n < 2^31 by multiply-high and shift.
@@ -151,6 +152,23 @@ struct PoolRowsK {
     FastDiv div_cbs, div_chunks, div_c;
 };
 
+// Two pooling operations in one register sliding-window kernel: pre, pool1, mid, pool2, post.
+struct PoolRows2K {
+    const void *in;
+    void *out;
+    const float *params;
+    int32_t *idx;     // index output of pool2 (pool1 never has one here)
+    int32_t n_pre, n_mid, n_post;
+    EwOp pre[K_MAX_EW], mid[K_MAX_EW], post[K_MAX_EW];
+    PoolK pool1, pool2;
+    int32_t C, H, W, H1, W1, Ho, Wo;  // input plane, plane between the pools, output plane
+    int32_t rc;       // output rows one lane walks down
+    int32_t chunks;   // chunks per plane = ceil(Ho / rc)
+    int32_t cbs;      // 128-bit column blocks per input row = W / vec
+    uint32_t total;   // lanes with work = planes * chunks * cbs
+    FastDiv div_cbs, div_chunks, div_c;
+};
+
 // Origin (global row / column of LDS cell 0,0) of every level's region for tile (ti, tj).
 // Used by the kernel and, with the same code, by the planner's bounds audit.
 struct Origins {
@@ -204,6 +222,7 @@ struct Sequence {
     StreamK stream{};
     PoolDirectK direct{};
     PoolRowsK rows{};
+    PoolRows2K rows2{};
     LdsSeqK lds{};
 };
 
@@ -263,6 +282,9 @@ void set_hip_error(int32_t e);
 // bs_rows.hip
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);
 bs_status launch_rows(const PoolRowsK &k, bool bf16, int64_t grid, int32_t threads, void *stream);
+// bs_rows2.hip
+bool rows2_supported(const PoolRows2K &k);
+bs_status launch_rows2(const PoolRows2K &k, bool bf16, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
 bool lds_fast_path(const LdsSeqK &k);
 bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);

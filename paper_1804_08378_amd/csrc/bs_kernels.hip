@@ -357,6 +357,14 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         break;
     }
     case BS_VARIANT_POOL_ROWS: {
+        if (q.n_levels == 2) {
+            PoolRows2K k = q.rows2;
+            k.in = in; k.out = out; k.params = s->dev_params;
+            k.idx = ip[0];
+            const bs_status ls = launch_rows2(k, bf16, q.grid, q.threads, stream);
+            if (ls != BS_OK) return ls;
+            break;
+        }
         PoolRowsK k = q.rows;
         k.in = in; k.out = out; k.params = s->dev_params;
         k.idx = ip[0];

@@ -419,10 +419,48 @@ static void plan_direct(const bs_stack *s, Sequence &q)
     q.n_levels = 1;
 }
 
+// Two consecutive pooling operations, BatchNorm and ReLU only around them, no index output on
+// the first, in shapes the two-level rows kernel is instantiated for.
+static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
+{
+    const int32_t vec = vec_of(s);
+    Sequence tmp;
+    Sequence &q = fill ? *fill : tmp;
+    PoolRows2K k{};
+    int seen = 0;
+    for (int32_t i = first_op; i < first_op + n_ops; ++i) {
+        const Op &op = s->ops[i];
+        if (!op_is_elementwise(op.kind)) {
+            if (seen == 0) {
+                if (op.idx_slot >= 0 || op.in_w % vec != 0) return false;
+                k.pool1 = make_pool(op, nullptr, q);
+                k.H = op.in_h; k.W = op.in_w; k.H1 = op.out_h; k.W1 = op.out_w;
+            } else {
+                k.pool2 = make_pool(op, nullptr, q);
+                k.Ho = op.out_h; k.Wo = op.out_w;
+            }
+            ++seen;
+        } else if (op.kind != OP_AVGNORM) {
+            if (op.kind == OP_ADD) return false;
+            int32_t &n = seen == 0 ? k.n_pre : (seen == 1 ? k.n_mid : k.n_post);
+            EwOp *list = seen == 0 ? k.pre : (seen == 1 ? k.mid : k.post);
+            if (n >= K_MAX_EW) return false;
+            fill_ew(s, op, q, list[n++]);
+        }
+    }
+    if (seen != 2 || !rows2_supported(k)) return false;
+    // every output column must fall under some lane's column block
+    const int32_t sws = k.pool1.sw * k.pool2.sw;
+    if (vec % sws != 0 || (int64_t)(k.W / vec) * (vec / sws) < k.Wo) return false;
+    if (fill) fill->rows2 = k;
+    return true;
+}
+
 // One pooling operation with overlapping / padded windows, BatchNorm and ReLU only around it,
-// in a shape the rows kernel is instantiated for.
+// in a shape the rows kernel is instantiated for -- or two such operations (rows2_applicable).
 static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
 {
+    if (count_pools(s, first_op, n_ops) == 2) return rows2_applicable(s, first_op, n_ops, fill);
     if (count_pools(s, first_op, n_ops) != 1) return false;
     const int32_t vec = vec_of(s);
     Sequence tmp;
@@ -448,11 +486,54 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
     return true;
 }
 
+static void plan_rows2(const bs_stack *s, Sequence &q, const bs_plan_options &o)
+{
+    PoolRows2K &k = q.rows2;
+    const int32_t vec = vec_of(s);
+    q.vec = vec;
+    q.threads = std::min(q.threads, 256);
+    k.C = (int32_t)q.in_shape[1];
+    const int64_t planes = q.in_shape[0] * q.in_shape[1];
+    k.cbs = k.W / vec;
+    // Output rows per lane: a chunk recomputes the level-1 rows and re-reads the input rows it
+    // shares with the chunk above, so chunks are longer than in the one-level kernel.
+    int32_t rc = std::min(K_ROWS2_RC, k.Ho);
+    if (o.tile_rows > 0) rc = std::min(o.tile_rows, k.Ho);
+    k.rc = std::max(1, rc);
+    k.chunks = (k.Ho + k.rc - 1) / k.rc;
+    k.total = (uint32_t)(planes * k.chunks * k.cbs);
+    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+    k.div_c = make_fastdiv((uint32_t)k.C);
+    q.grid = ((int64_t)k.total + q.threads - 1) / q.threads;
+    q.lds_bytes = 0;
+    q.tile_rows = k.rc;
+    q.tile_cols = k.Wo;
+    q.planes_per_group = 0;
+    q.n_levels = 2;
+    const int32_t r0 = (k.pool2.kh - 1) * k.pool1.sh + k.pool1.kh;  // input rows under one output row
+    q.halo_rows = std::max(0, r0 - k.pool1.sh * k.pool2.sh);
+    q.halo_cols = k.pool2.pw * k.pool1.sw + k.pool1.pw;
+    double rows_loaded = 0;
+    for (int32_t ch = 0; ch < k.chunks; ++ch) {
+        const int32_t a = ch * k.rc, b = std::min(k.Ho, a + k.rc);
+        const int32_t lo1 = a * k.pool2.sh - k.pool2.ph, hi1 = (b - 1) * k.pool2.sh - k.pool2.ph + k.pool2.kh;
+        const int32_t lo = std::max(0, lo1 * k.pool1.sh - k.pool1.ph);
+        const int32_t hi = std::min(k.H, (hi1 - 1) * k.pool1.sh - k.pool1.ph + k.pool1.kh);
+        rows_loaded += std::max(0, hi - lo);
+    }
+    q.redundancy = rows_loaded / (double)k.H;
+}
+
 static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, const Limits &lim)
 {
     q.variant = BS_VARIANT_POOL_ROWS;
     q.n_idx = 0;
     rows_applicable(s, q.first_op, q.n_ops, &q);
+    if (count_pools(s, q.first_op, q.n_ops) == 2) {
+        plan_rows2(s, q, o);
+        return;
+    }
     PoolRowsK &k = q.rows;
     const int32_t vec = vec_of(s);
     q.vec = vec;
@@ -463,7 +544,8 @@ static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, 
     // Output rows per lane.  Measured on MI355X, short chunks win: the kh - sh rows two vertically
     // adjacent chunks share are requested by lanes of the same wave within a few instructions and
     // are served by the L1/L2 caches, while long chunks leave each lane a chain of dependent
-    // memory round trips.  Two rows per lane were fastest for the 112x112 and 56x56 planes tried.
+    // memory round trips.  With two rows per lane (and the kernel producing two output rows per
+    // iteration) a lane requests all its input rows at once: one round trip per wave.
     int32_t rc = std::min(2, k.Ho);
     (void)lim;
     if (o.tile_rows > 0) rc = std::min(o.tile_rows, k.Ho);

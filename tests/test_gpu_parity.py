@@ -268,6 +268,35 @@ def test_pool_rows_kernel(shape, dtype):
         assert info["sequences"][0]["variant_name"] == "lds_tile"
 
 
+def _rows2_stacks(c):
+    return {
+        "halo": [wl.bn_params(c, 65), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1, True),
+                 wl.bn_params(c, 66), wl.relu()],
+        "halo_in_range_count": [wl.bn_params(c, 65), wl.relu(), wl.avgpool(3, 1, 1, False), wl.maxpool(3, 2, 1, False),
+                                wl.bn_params(c, 66), wl.relu()],
+        "blocks2": [wl.maxpool(3, 1, 1, False), wl.bn_params(c, 67), wl.relu(),
+                    wl.maxpool(3, 1, 1, True), wl.bn_params(c, 68), wl.relu()],
+        "listing2": [wl.maxpool(3, 1, 1, False), wl.bn_params(c, 69), wl.relu(), wl.avgpool(3, 1, 1, True)],
+    }
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 12, 16), (1, 2, 9, 8), (3, 5, 33, 24), (1, 4, 64, 64), (1, 1, 3, 8),
+                                   (1, 2, 1, 8), (2, 2, 2, 16)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pool_rows2_kernel(shape, dtype):
+    """Two pooling steps in one sequence through the two-level register-sliding kernel, for
+    several chunk lengths (1 row per lane, ragged, whole plane), and the same stacks through
+    the LDS kernels."""
+    for name, layers in _rows2_stacks(shape[1]).items():
+        x = wl.activation(shape, 71, dtype)
+        for rc in (0, 1, 3, 1000):
+            info = check(layers, x, [], dtype, f"rows2/{name}{shape}/rc{rc}", tile_rows=rc)
+            assert info["n_sequences"] == 1, name
+            assert info["sequences"][0]["variant_name"] == "pool_rows", name
+        info = check(layers, x, [], dtype, f"rows2/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
+        assert [q["variant_name"] for q in info["sequences"]] == ["lds_tile"] * info["n_sequences"]
+
+
 # ------------------------------------------------------------------ special values
 def test_signed_zero_and_subnormals_follow_the_oracle():
     """ReLU maps -0 to +0, subnormal values pass through unchanged, and max pooling of windows
