@@ -57,7 +57,8 @@ typedef enum bs_status {
     BS_ERR_HIP = 9,         /* a HIP call failed; see bs_last_hip_error()                  */
     BS_ERR_ALLOC = 10,      /* host allocation failed                                      */
     BS_ERR_RANGE = 11,      /* an index argument is out of range                           */
-    BS_ERR_ALIAS = 12       /* out overlaps an input where that is not allowed             */
+    BS_ERR_ALIAS = 12,      /* out overlaps an input where that is not allowed             */
+    BS_ERR_JIT = 13         /* a run-time kernel build the caller required has failed      */
 } bs_status;
 
 typedef enum bs_dtype { BS_F32 = 0, BS_BF16 = 1 } bs_dtype;
@@ -128,6 +129,15 @@ typedef enum bs_variant {
  *                           final-output tile of LDS sequences (0 = automatic)
  *   host_only               != 0: plan without touching any device; such a plan can be
  *                           inspected but bs_stack_run returns BS_ERR_NOT_PLANNED
+ *   jit                     run-time kernel builds (Section 4.1: code is generated for the
+ *                           stack and compiled when it is optimised).  A sequence whose
+ *                           signature (pooling shapes, element-wise lists) has no instance
+ *                           compiled into the library gets one built with hipRTC during
+ *                           bs_stack_plan; builds are shared by all stacks of the process.
+ *                           0 = automatic: on unless the environment has BS_JIT=0; if a
+ *                           build fails the plan falls back to the slower kernels that read
+ *                           shapes at run time.  1 = required: a failed build makes
+ *                           bs_stack_plan return BS_ERR_JIT.  -1 = off for this plan.
  */
 typedef struct bs_plan_options {
     uint64_t max_lds_bytes;
@@ -138,7 +148,8 @@ typedef struct bs_plan_options {
     int32_t force_variant;
     int32_t tile_rows, tile_cols, planes_per_group;
     int32_t host_only;
-    int32_t reserved[5];
+    int32_t jit;
+    int32_t reserved[4];
 } bs_plan_options;
 
 typedef struct bs_plan_info {
@@ -169,6 +180,9 @@ typedef struct bs_sequence_info {
     uint64_t lds_bytes;
     int64_t in_shape[4], out_shape[4];
     double redundancy;               /* elements loaded (with halos) / elements of the input */
+    int32_t run_time_build;          /* 1: the kernel was (or, host-only, would be) built for this
+                                        signature at plan time; 0: compiled into the library   */
+    int32_t reserved;
 } bs_sequence_info;
 
 
@@ -208,7 +222,8 @@ BS_API bs_status bs_stack_folded_bn(const bs_stack *stack, int32_t layer, float 
  * opts->host_only is set it queries the current HIP device for limits that opts
  * leaves at 0 and uploads the folded BatchNorm parameters (library-owned device
  * memory, freed by bs_stack_destroy or a re-plan).  May be called again.
- * Errors: BS_ERR_NULL, BS_ERR_PARAM (bad option), BS_ERR_NO_FIT, BS_ERR_HIP, BS_ERR_ALLOC.
+ * Errors: BS_ERR_NULL, BS_ERR_PARAM (bad option), BS_ERR_NO_FIT, BS_ERR_HIP, BS_ERR_ALLOC,
+ *         BS_ERR_JIT (opts->jit == 1 only; bs_jit_log() has the compiler output).
  */
 BS_API bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts);
 
@@ -242,6 +257,18 @@ BS_API uint64_t bs_stack_workspace_bytes(const bs_stack *stack);
 BS_API bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,
                               void *out, int32_t *const *indices, void *workspace,
                               uint64_t workspace_bytes, void *stream);
+
+/*
+ * Compile, without loading them and without touching any device, all run-time builds the
+ * current plan (device or host-only) asks for, for GPU architecture `arch` ("gfx950"; NULL =
+ * "gfx950").  A way to check on a machine without a GPU that a stack's kernels build.
+ * `n_built`, if not NULL, receives the number of kernels compiled.
+ * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED (no plan at all), BS_ERR_JIT (see bs_jit_log()).
+ */
+BS_API bs_status bs_stack_jit_check(const bs_stack *stack, const char *arch, int32_t *n_built);
+/* Compiler output of the calling process's last failed run-time build ("" if none); the
+ * pointer stays valid until the calling thread's next call of this function. */
+BS_API const char *bs_jit_log(void);
 
 /* Static, never NULL. */
 BS_API const char *bs_status_string(bs_status status);

@@ -25,7 +25,7 @@ VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows"}
 STATUS_NAMES = {
     0: "BS_OK", 1: "BS_ERR_NULL", 2: "BS_ERR_SHAPE", 3: "BS_ERR_PARAM", 4: "BS_ERR_UNSUPPORTED",
     5: "BS_ERR_NOT_PLANNED", 6: "BS_ERR_NO_FIT", 7: "BS_ERR_ALIGN", 8: "BS_ERR_WORKSPACE",
-    9: "BS_ERR_HIP", 10: "BS_ERR_ALLOC", 11: "BS_ERR_RANGE", 12: "BS_ERR_ALIAS",
+    9: "BS_ERR_HIP", 10: "BS_ERR_ALLOC", 11: "BS_ERR_RANGE", 12: "BS_ERR_ALIAS", 13: "BS_ERR_JIT",
 }
 
 _f32p = C.POINTER(C.c_float)
@@ -46,7 +46,7 @@ class bs_plan_options(C.Structure):
                 ("max_steps_per_sequence", C.c_int32), ("threads_per_group", C.c_int32),
                 ("num_cus", C.c_int32), ("breadth_first", C.c_int32), ("force_variant", C.c_int32),
                 ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("planes_per_group", C.c_int32),
-                ("host_only", C.c_int32), ("reserved", C.c_int32 * 5)]
+                ("host_only", C.c_int32), ("jit", C.c_int32), ("reserved", C.c_int32 * 4)]
 
 
 class bs_plan_info(C.Structure):
@@ -67,7 +67,8 @@ class bs_sequence_info(C.Structure):
                 ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("planes_per_group", C.c_int32),
                 ("halo_rows", C.c_int32), ("halo_cols", C.c_int32), ("threads_per_group", C.c_int32),
                 ("grid", C.c_int64), ("lds_bytes", C.c_uint64),
-                ("in_shape", C.c_int64 * 4), ("out_shape", C.c_int64 * 4), ("redundancy", C.c_double)]
+                ("in_shape", C.c_int64 * 4), ("out_shape", C.c_int64 * 4), ("redundancy", C.c_double),
+                ("run_time_build", C.c_int32), ("reserved", C.c_int32)]
 
 
 _lib = None
@@ -90,6 +91,8 @@ _SIGNATURES = {
     "bs_stack_workspace_bytes": (C.c_uint64, [C.c_void_p]),
     "bs_stack_run": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
                                C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_stack_jit_check": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]),
+    "bs_jit_log": (C.c_char_p, []),
     "bs_status_string": (C.c_char_p, [C.c_int]),
     "bs_version": (C.c_char_p, []),
     "bs_last_hip_error": (C.c_int32, []),
@@ -121,6 +124,8 @@ class BrainSlugError(RuntimeError):
         extra = ""
         if self.status == 9:
             extra = f" (hipError_t {load().bs_last_hip_error()})"
+        if self.status == 13:
+            extra = "\n" + load().bs_jit_log().decode(errors="replace")[-4000:]
         super().__init__(f"{where}: {STATUS_NAMES.get(self.status, self.status)}: {msg}{extra}")
 
 
@@ -140,6 +145,17 @@ def bs_status_string(status: int) -> str:
 
 def bs_last_hip_error() -> int:
     return int(load().bs_last_hip_error())
+
+
+def bs_jit_log() -> str:
+    return load().bs_jit_log().decode(errors="replace")
+
+
+def bs_stack_jit_check(handle, arch: str = "gfx950") -> int:
+    """Compile (only) the plan's run-time builds for `arch`; returns how many were compiled."""
+    n = C.c_int32(0)
+    _check(load().bs_stack_jit_check(C.c_void_p(handle), arch.encode(), C.byref(n)), "bs_stack_jit_check")
+    return int(n.value)
 
 
 def _shape4(shape):

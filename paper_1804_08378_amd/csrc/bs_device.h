@@ -2,12 +2,16 @@
 // 128-bit register blocks and their loads / stores.
 #pragma once
 
+#if !defined(__HIPCC_RTC__)
 #include <hip/hip_runtime.h>
 
 #include <cmath>
-#include <cstdint>
+#endif
+#if !defined(INFINITY)
+#define INFINITY __builtin_inff()
+#endif
 
-#include "bs_internal.h"
+#include "bs_kargs.h"
 
 namespace bs {
 

@@ -7,24 +7,9 @@
 #include <vector>
 
 #include "brainslug.h"
+#include "bs_kargs.h"
 
 namespace bs {
-
-// ---------------------------------------------------------------------------
-// Basic operations a layer maps to (Section 4.1 "collapse process": layers are
-// mapped onto element-wise and non-element-wise operations; Listing 2 shows
-// average pooling as AvgPooling + AvgNormalization).
-// ---------------------------------------------------------------------------
-enum OpKind : int32_t {
-    OP_BN = 1,
-    OP_RELU = 2,
-    OP_ADD = 3,
-    OP_MAXPOOL = 4,
-    OP_AVGSUM = 5,   // non-element-wise: window sum
-    OP_AVGNORM = 6,  // element-wise: multiply by 1/divisor
-};
-
-inline bool op_is_elementwise(int32_t k) { return k != OP_MAXPOOL && k != OP_AVGSUM; }
 
 struct Op {
     int32_t kind = 0;
@@ -41,163 +26,7 @@ struct Step {
     int32_t first_op = 0, n_ops = 0, pool_op = -1, sequence = -1;
 };
 
-// ---------------------------------------------------------------------------
-// Kernel argument blocks (plain data, passed by value at launch).
-// ---------------------------------------------------------------------------
-constexpr int K_MAX_LEVELS = 8;   // pooling operations in one LDS sequence
-constexpr int K_MAX_EW = 6;       // element-wise operations attached to one level
-constexpr int K_MAX_STREAM_EW = 16;
-constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
-constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
-constexpr int K_STREAM_U = 4;     // 128-bit vectors per lane in stream_kernel
-constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
-constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
-
-// n / d for 0 <= n < 2^31 by multiply-high and shift.
-struct FastDiv {
-    uint32_t mul = 0, shift = 0, d = 1;
-};
 FastDiv make_fastdiv(uint32_t d);
-
-struct EwOp {
-    int32_t kind;  // OP_BN, OP_RELU, OP_ADD
-    int32_t arg;   // BN: offset of scale[] in the parameter table; Add: residual slot of the sequence
-};
-
-struct PoolK {
-    int32_t kind;  // OP_MAXPOOL or OP_AVGSUM (normalisation included)
-    int32_t kh, kw, sh, sw, ph, pw;
-    int32_t count_include_pad;
-    int32_t idx_slot;  // slot in LdsSeqK::idx, or -1
-    float inv_kk;      // 1.0f / (kh * kw)
-};
-
-// One level of an LDS sequence.  The region a work-group keeps of level l is a fixed-size
-// rectangle rows x cols whose origin (which may lie outside the plane: padding) follows
-// from the tile by origin[l-1] = origin[l] * stride - pad.
-struct LevelK {
-    int32_t H, W;            // plane size at this level
-    int32_t rows, cols;      // region extent; cols is a multiple of 4 for levels >= 1
-    int32_t pitch;           // LDS row pitch in floats (multiple of 4)
-    int32_t plane_stride;    // rows * pitch
-    int32_t buf_off;         // float offset of this level's buffer in dynamic LDS
-    int32_t n_ew;
-    EwOp ew[K_MAX_EW];       // applied to a value once it exists at this level
-    int32_t vo;              // outputs one lane produces per strip at this level (levels >= 1)
-    int32_t items_per_row;   // level 0: global vectors per region row; else strips of vo outputs
-    int32_t ct, rt;          // lane grid of a phase: ct = min(items_per_row, threads) lanes along a
-                             // row, rt = threads / ct rows in flight
-    FastDiv div_ct;          // by ct
-};
-
-struct LdsSeqK {
-    const void *in;
-    void *out;
-    const float *params;
-    const void *res[K_MAX_RES];
-    int32_t *idx[K_MAX_IDX];
-    int32_t n_levels;  // L >= 1 pooling operations; levels 0..L
-    int32_t NC, C;
-    int32_t TH, TW, tiles_h, tiles_w, PPG;
-    int32_t vec;       // elements per 128-bit access used for the level-0 load (1 = scalar)
-    int32_t delta0;    // level-0 LDS column of the region's first column: the LDS row starts at the
-                       // 128-bit global vector that contains it (0 when vec == 1)
-    FastDiv div_tiles_w, div_tiles_hw, div_c;
-    LevelK level[K_MAX_LEVELS + 1];
-    PoolK pool[K_MAX_LEVELS + 1];  // pool[l] produces level l from level l-1 (l >= 1)
-};
-
-struct StreamK {
-    const void *in;
-    void *out;
-    const float *params;
-    const void *res[K_MAX_RES];
-    int32_t n_ew;
-    EwOp ew[K_MAX_STREAM_EW];
-    uint32_t total;     // vectors (or elements when vec == 1)
-    int32_t C;
-    FastDiv div_plane;  // by H*W/vec
-    FastDiv div_c;
-};
-
-struct PoolDirectK {
-    const void *in;
-    void *out;
-    const float *params;
-    const void *res[K_MAX_RES];
-    int32_t *idx;
-    int32_t n_pre, n_post;
-    EwOp pre[K_MAX_EW], post[K_MAX_EW];
-    PoolK pool;
-    int32_t C, H, W, Ho, Wo;
-    uint32_t total;      // units = planes * Ho * (W / vec)
-    FastDiv div_wv;      // by W / vec
-    FastDiv div_ho;      // by Ho
-    FastDiv div_c;
-};
-
-struct PoolRowsK {
-    const void *in;
-    void *out;
-    const float *params;
-    int32_t *idx;
-    int32_t n_pre, n_post;
-    EwOp pre[K_MAX_EW], post[K_MAX_EW];
-    PoolK pool;
-    int32_t C, H, W, Ho, Wo;
-    int32_t rc;       // output rows one lane walks down
-    int32_t chunks;   // chunks per plane = ceil(Ho / rc)
-    int32_t cbs;      // 128-bit column blocks per input row = W / vec
-    uint32_t total;   // lanes with work = planes * chunks * cbs
-    FastDiv div_cbs, div_chunks, div_c;
-};
-
-// Two pooling operations in one register sliding-window kernel: pre, pool1, mid, pool2, post.
-struct PoolRows2K {
-    const void *in;
-    void *out;
-    const float *params;
-    int32_t *idx;     // index output of pool2 (pool1 never has one here)
-    int32_t n_pre, n_mid, n_post;
-    EwOp pre[K_MAX_EW], mid[K_MAX_EW], post[K_MAX_EW];
-    PoolK pool1, pool2;
-    int32_t C, H, W, H1, W1, Ho, Wo;  // input plane, plane between the pools, output plane
-    int32_t rc;       // output rows one lane walks down
-    int32_t chunks;   // chunks per plane = ceil(Ho / rc)
-    int32_t cbs;      // 128-bit column blocks per input row = W / vec
-    uint32_t total;   // lanes with work = planes * chunks * cbs
-    FastDiv div_cbs, div_chunks, div_c;
-};
-
-// Origin (global row / column of LDS cell 0,0) of every level's region for tile (ti, tj).
-// Used by the kernel and, with the same code, by the planner's bounds audit.
-struct Origins {
-    int32_t r[K_MAX_LEVELS + 1], c[K_MAX_LEVELS + 1];
-};
-
-#if defined(__HIPCC__)
-#define BS_HD __host__ __device__ inline
-#else
-#define BS_HD inline
-#endif
-
-// Outputs one lane produces per strip of a pooling phase, by column stride.  Two per lane for
-// stride 2 would make consecutive lanes read LDS four floats apart (no bank conflicts), but it
-// doubles the per-output address and predicate work; measured on MI355X four per lane is faster
-// for every BASELINE stack, so the rule is constant.  Planner, audit and kernels all use it.
-#if defined(__HIPCC__)
-__host__ __device__
-#endif
-constexpr int32_t strip_outputs(int32_t sw)
-{
-    return sw >= 1 ? 4 : 4;
-}
-
-BS_HD void origin_step(const PoolK &p, int32_t &r0, int32_t &c0)
-{
-    r0 = r0 * p.sh - p.ph;
-    c0 = c0 * p.sw - p.pw;
-}
 
 enum KernelId : int32_t { KERNEL_STREAM = 1, KERNEL_POOL_DIRECT = 2, KERNEL_LDS = 3 };
 
@@ -224,6 +53,9 @@ struct Sequence {
     PoolRowsK rows{};
     PoolRows2K rows2{};
     LdsSeqK lds{};
+    // run-time build (hipFunction_t) without / with index outputs; null = pre-compiled kernel
+    int32_t jit = 0;
+    void *jit_fn[2] = {nullptr, nullptr};
 };
 
 struct Layer {
@@ -261,6 +93,7 @@ struct bs_stack {
     uint64_t workspace_bytes = 0;
     uint64_t ws_half_bytes = 0;  // size of each of the two ping-pong halves
     uint64_t algorithmic_bytes = 0;
+    bool jit_failed = false;  // a run-time build failed during this plan: plan again without
 };
 
 namespace bs {
@@ -279,14 +112,29 @@ void free_params(bs_stack *s);
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
                           const void *const *res, int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
-// bs_rows.hip
+// bs_rows.hip: *_supported = the signature is in the pre-compiled table; *_buildable = the
+// kernel template can be instantiated for it at run time; *_expr = that instance's name
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);
+bool rows_buildable(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post, int32_t vec);
+std::string rows_expr(const PoolRowsK &k, bool bf16, bool want_idx);
 bs_status launch_rows(const PoolRowsK &k, bool bf16, int64_t grid, int32_t threads, void *stream);
 // bs_rows2.hip
 bool rows2_supported(const PoolRows2K &k);
+bool rows2_buildable(const PoolRows2K &k, int32_t vec);
+std::string rows2_expr(const PoolRows2K &k, bool bf16, bool want_idx);
 bs_status launch_rows2(const PoolRows2K &k, bool bf16, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
 bool lds_fast_path(const LdsSeqK &k);
+bool lds_precompiled(const LdsSeqK &k, bool bf16);
+bool lds_buildable(const LdsSeqK &k);
+std::string lds_expr(const LdsSeqK &k, bool bf16, bool want_idx);
 bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
+// bs_jit.cpp
+bool jit_enabled();
+std::string jit_last_log();
+bool jit_check(const std::string &header, const std::string &expr, const std::string &arch);
+bs_status jit_kernel(const std::string &header, const std::string &expr, void **fn);
+bs_status jit_launch(void *fn, const void *args, size_t arg_bytes, int64_t grid, int32_t threads, uint64_t lds_bytes,
+                     void *stream);
 
 }  // namespace bs

@@ -25,6 +25,7 @@
 // With bfloat16 storage every layer's output is rounded to bfloat16 (nearest-even).
 // No MFMA: the path moves 5..12 bytes per element and does ~10 flops on them.
 #include "bs_device.h"
+#include "bs_internal.h"
 
 namespace bs {
 
@@ -321,6 +322,14 @@ static void launch_direct(const PoolDirectK &k, dim3 grid, dim3 block, hipStream
     }
 }
 
+// Launch the sequence's run-time build (compiled at plan time) with argument block `args`.
+static bs_status launch_built(const Sequence &q, bool want_idx, const void *args, size_t bytes, void *stream)
+{
+    void *fn = q.jit_fn[want_idx ? 1 : 0];
+    if (!fn) return BS_ERR_NOT_PLANNED;
+    return jit_launch(fn, args, bytes, q.grid, q.threads, q.lds_bytes, stream);
+}
+
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
                           const void *const *res, int32_t *const *idx, void *stream)
 {
@@ -361,14 +370,18 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
             PoolRows2K k = q.rows2;
             k.in = in; k.out = out; k.params = s->dev_params;
             k.idx = ip[0];
-            const bs_status ls = launch_rows2(k, bf16, q.grid, q.threads, stream);
+            const bool want_idx = k.idx != nullptr && k.pool2.kind == OP_MAXPOOL;
+            const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
+                                       : launch_rows2(k, bf16, q.grid, q.threads, stream);
             if (ls != BS_OK) return ls;
             break;
         }
         PoolRowsK k = q.rows;
         k.in = in; k.out = out; k.params = s->dev_params;
         k.idx = ip[0];
-        const bs_status ls = launch_rows(k, bf16, q.grid, q.threads, stream);
+        const bool want_idx = k.idx != nullptr && k.pool.kind == OP_MAXPOOL;
+        const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
+                                   : launch_rows(k, bf16, q.grid, q.threads, stream);
         if (ls != BS_OK) return ls;
         break;
     }
@@ -377,7 +390,10 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         for (int j = 0; j < K_MAX_IDX; ++j) k.idx[j] = ip[j];
-        const bs_status ls = launch_lds(k, bf16, q.grid, q.threads, q.lds_bytes, stream);
+        bool want_idx = false;
+        for (int j = 0; j < q.n_idx; ++j) want_idx = want_idx || ip[j] != nullptr;
+        const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
+                                   : launch_lds(k, bf16, q.grid, q.threads, q.lds_bytes, stream);
         if (ls != BS_OK) return ls;
         break;
     }

@@ -419,8 +419,14 @@ static void plan_direct(const bs_stack *s, Sequence &q)
     q.n_levels = 1;
 }
 
+// May this plan rely on run-time kernel builds for signatures without a pre-compiled instance?
+static bool jit_allowed(const bs_stack *s)
+{
+    return s->opts.jit >= 0 && !s->jit_failed && jit_enabled();
+}
+
 // Two consecutive pooling operations, BatchNorm and ReLU only around them, no index output on
-// the first, in shapes the two-level rows kernel is instantiated for.
+// the first, in shapes the two-level rows kernel is instantiated for (or can be built for).
 static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
 {
     const int32_t vec = vec_of(s);
@@ -448,7 +454,8 @@ static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
             fill_ew(s, op, q, list[n++]);
         }
     }
-    if (seen != 2 || !rows2_supported(k)) return false;
+    if (seen != 2) return false;
+    if (!rows2_supported(k) && !(jit_allowed(s) && rows2_buildable(k, vec))) return false;
     // every output column must fall under some lane's column block
     const int32_t sws = k.pool1.sw * k.pool2.sw;
     if (vec % sws != 0 || (int64_t)(k.W / vec) * (vec / sws) < k.Wo) return false;
@@ -481,7 +488,12 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
             else fill_ew(s, op, q, k.pre[k.n_pre++]);
         }
     }
-    if (!rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) return false;
+    if (!seen) return false;
+    if (!rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post) &&
+        !(jit_allowed(s) && rows_buildable(k.pool, k.pre, k.n_pre, k.post, k.n_post, vec)))
+        return false;
+    // every output column must fall under some lane's column block
+    if ((int64_t)(k.W / vec) * (vec / k.pool.sw) < k.Wo) return false;
     if (fill) fill->rows = k;
     return true;
 }
@@ -581,6 +593,7 @@ static bool seq_is_fast(const bs_stack *s, int32_t first_op, int32_t n_ops)
     if (count_pools(s, first_op, n_ops) == 0) return true;
     if (direct_applicable(s, first_op, n_ops) || rows_applicable(s, first_op, n_ops, nullptr)) return true;
     if (!seq_capacity_ok(s, first_op, n_ops, false)) return false;
+    if (jit_allowed(s)) return true;  // any signature gets its own build
     Sequence tmp;
     LdsSeqK k{};
     int level = 0;
@@ -797,6 +810,51 @@ static bool audit_lds(const Sequence &q)
 // sequence is closed and a new one starts with that step.  The trailing sequence
 // is kept.  A step-count cap implements the strategies of Section 5.1.
 // ---------------------------------------------------------------------------
+// Header and template-instance names (without / with index outputs) of a sequence's run-time build.
+static const char *jit_names(const bs_stack *s, const Sequence &q, std::string (&expr)[2])
+{
+    const bool bf16 = s->dtype == BS_BF16;
+    for (int w = 0; w < 2; ++w) {
+        if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) expr[w] = rows2_expr(q.rows2, bf16, w != 0);
+        else if (q.variant == BS_VARIANT_POOL_ROWS) expr[w] = rows_expr(q.rows, bf16, w != 0);
+        else expr[w] = lds_expr(q.lds, bf16, w != 0);
+    }
+    return q.variant == BS_VARIANT_POOL_ROWS ? "bs_rows_device.h" : "bs_lds_device.h";
+}
+
+// Decide whether the sequence runs a pre-compiled kernel or a run-time build, and (unless
+// the plan is host-only) compile the latter now: without index outputs, and with them if
+// the sequence has any.  A failed build marks the stack so that it is planned again without.
+static bs_status prepare_jit(bs_stack *s, Sequence &q, bool host_only)
+{
+    q.jit = 0;
+    q.jit_fn[0] = q.jit_fn[1] = nullptr;
+    const bool bf16 = s->dtype == BS_BF16;
+    if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) {
+        if (rows2_supported(q.rows2)) return BS_OK;
+    } else if (q.variant == BS_VARIANT_POOL_ROWS) {
+        const PoolRowsK &k = q.rows;
+        if (rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) return BS_OK;
+    } else if (q.variant == BS_VARIANT_LDS_TILE) {
+        if (lds_precompiled(q.lds, bf16) || !jit_allowed(s) || !lds_buildable(q.lds)) return BS_OK;
+    } else {
+        return BS_OK;
+    }
+    std::string expr[2];
+    const char *header = jit_names(s, q, expr);
+    const bool idx_variant = q.n_idx > 0;
+    q.jit = 1;
+    if (host_only) return BS_OK;
+    for (int w = 0; w < (idx_variant ? 2 : 1); ++w) {
+        const bs_status st = jit_kernel(header, expr[w], &q.jit_fn[w]);
+        if (st != BS_OK) {
+            s->jit_failed = true;
+            return BS_ERR_JIT;
+        }
+    }
+    return BS_OK;
+}
+
 bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &lim)
 {
     s->seqs.clear();
@@ -875,6 +933,8 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             st = plan_lds(s, q, o, lim);
         }
         if (st != BS_OK) return st;
+        st = prepare_jit(s, q, o.host_only != 0);
+        if (st != BS_OK) return st;
         if (di + 1 < drafts.size()) {
             uint64_t bytes = (uint64_t)q.out_shape[0] * q.out_shape[1] * q.out_shape[2] * q.out_shape[3] * es;
             max_inter = std::max(max_inter, bytes);
@@ -906,6 +966,7 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
         return BS_ERR_PARAM;
     if (o.force_variant < 0 || o.force_variant > BS_VARIANT_POOL_ROWS) return BS_ERR_PARAM;
     if (o.max_lds_bytes > 64 * 1024) return BS_ERR_PARAM;
+    if (o.jit < -1 || o.jit > 1) return BS_ERR_PARAM;
 
     stack->planned = stack->device_planned = false;
     free_params(stack);
@@ -927,11 +988,15 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (lim.max_lds_bytes == 0) lim.max_lds_bytes = 32 * 1024;
 
     stack->opts = o;
+    stack->jit_failed = false;
     bs_status st;
     try {
         st = build_operations(stack);
         if (st == BS_OK) st = group_steps(stack);
         if (st == BS_OK) st = group_sequences(stack, o, lim);
+        // a run-time build failed: unless the caller insists on them, plan with the
+        // pre-compiled and run-time-shape kernels only
+        if (st == BS_ERR_JIT && o.jit == 0) st = group_sequences(stack, o, lim);
     } catch (const std::bad_alloc &) {
         st = BS_ERR_ALLOC;
     }
@@ -952,6 +1017,31 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
         stack->device_planned = true;
     }
     return BS_OK;
+}
+
+bs_status bs_stack_jit_check(const bs_stack *stack, const char *arch, int32_t *n_built)
+{
+    if (!stack) return BS_ERR_NULL;
+    if (!stack->planned) return BS_ERR_NOT_PLANNED;
+    int32_t n = 0;
+    for (const Sequence &q : stack->seqs) {
+        if (!q.jit) continue;
+        std::string expr[2];
+        const char *header = jit_names(stack, q, expr);
+        for (int w = 0; w < (q.n_idx > 0 ? 2 : 1); ++w) {
+            if (!jit_check(header, expr[w], arch ? arch : "gfx950")) return BS_ERR_JIT;
+            ++n;
+        }
+    }
+    if (n_built) *n_built = n;
+    return BS_OK;
+}
+
+const char *bs_jit_log(void)
+{
+    static thread_local std::string copy;
+    copy = jit_last_log();
+    return copy.c_str();
 }
 
 bs_status bs_stack_plan_info(const bs_stack *stack, bs_plan_info *info)
@@ -1002,6 +1092,8 @@ bs_status bs_stack_sequence_info(const bs_stack *stack, int32_t sequence, bs_seq
     std::memcpy(r.in_shape, q.in_shape, sizeof(r.in_shape));
     std::memcpy(r.out_shape, q.out_shape, sizeof(r.out_shape));
     r.redundancy = q.redundancy;
+    r.run_time_build = q.jit;
+    r.reserved = 0;
     *info = r;
     return BS_OK;
 }

@@ -1,270 +1,12 @@
-// pool_rows2_kernel: two pooling operations in a row (each with element-wise operations
-// around it) without LDS -- a two-step sequence of Section 4.1 whose intermediate values
-// pass from step to step in registers instead of through the on-chip buffers of Section 4.4.
-//
-// A lane owns one 128-bit column block of the input plane (VEC columns -> VEC / (sw1 * sw2)
-// final outputs per output row) and walks down a chunk of rc output rows.  It keeps two
-// register windows: the kh1 level-0 rows (input after the leading element-wise operations)
-// under the level-1 row being produced, and the kh2 level-1 rows (first pool's output after
-// the middle element-wise operations) under the current output row.  Per output row it loads
-// sh1 * sh2 new input rows, produces sh2 new level-1 rows and one output row.  Horizontally a
-// lane recomputes the few level-1 columns its windows share with its neighbours, and reads
-// the level-0 columns those need left and right of its block with scalar loads that hit the
-// lines the neighbouring lanes fetch: lanes never exchange data, so there is no barrier.
-//
-// Cells outside a pooling operation's own input plane are that operation's padding
-// (-inf for max, +0 for average) and are never computed from earlier layers.
-#include "bs_rows.h"
+// Host side of pool_rows2_kernel: signature table, applicability test and launcher.
+#include <cstdio>
+#include <string>
+#include <type_traits>
+
+#include "bs_rows_device.h"
+#include "bs_internal.h"
 
 namespace bs {
-
-template <bool BF16, int VEC, class P1, class P2, int EW0, int EW1, int EW2, bool WANT_IDX>
-__global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
-{
-    constexpr int KH1 = P1::kh, KW1 = P1::kw, SH1 = P1::sh, SW1 = P1::sw, PH1 = P1::ph, PW1 = P1::pw;
-    constexpr int KH2 = P2::kh, KW2 = P2::kw, SH2 = P2::sh, SW2 = P2::sw, PH2 = P2::ph, PW2 = P2::pw;
-    constexpr int VB = VEC / SW1;                 // level-1 columns under the lane's block
-    constexpr int VO = VB / SW2;                  // outputs per lane per output row
-    constexpr int NC1 = (VO - 1) * SW2 + KW2;     // level-1 columns the VO windows span
-    constexpr int NL = PW2 * SW1 + PW1;           // level-0 columns left of the block
-    constexpr int NC0 = (NC1 - 1) * SW1 + KW1;    // level-0 columns the NC1 windows span
-    constexpr int NX = NC0 - NL - VEC;            // level-0 columns right of the block
-    constexpr int KEEP0 = KH1 - SH1;              // level-0 rows two consecutive level-1 rows share
-    constexpr int KEEP1 = KH2 - SH2;              // level-1 rows two consecutive output rows share
-    constexpr int R0 = (KH2 - 1) * SH1 + KH1;     // level-0 rows under one output row
-    constexpr int NS0 = SH1 * SH2;                // new level-0 rows per output row
-    constexpr int ES = BF16 ? 2 : 4;
-    constexpr bool MAX1 = P1::kind == OP_MAXPOOL, MAX2 = P2::kind == OP_MAXPOOL;
-    static_assert(VEC % (SW1 * SW2) == 0 && NX >= 0 && KEEP0 >= 0 && KEEP1 >= 0, "unsupported pooling shapes");
-    using E0 = RowsEw<EW0>;
-    using E1 = RowsEw<EW1>;
-    using E2 = RowsEw<EW2>;
-    const float pad0 = MAX1 ? -INFINITY : 0.0f;  // value of a cell outside the level-0 plane
-    const float pad1 = MAX2 ? -INFINITY : 0.0f;  // value of a cell outside the level-1 plane
-
-    // lane -> (plane, chunk, column block j), column block fastest
-    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    const bool live = i < k.total;
-    i = live ? i : 0u;
-    const uint32_t t = fdiv(i, k.div_cbs);
-    const int32_t j = (int32_t)(i - t * (uint32_t)k.cbs);
-    const uint32_t plane = fdiv(t, k.div_chunks);
-    const int32_t chunk = (int32_t)(t - plane * (uint32_t)k.chunks);
-    const int32_t c = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
-
-    RowsParams<E0> p0;
-    RowsParams<E1> p1;
-    RowsParams<E2> p2;
-    rows_load_params<E0>(k.pre, k.params, k.C, c, p0);
-    rows_load_params<E1>(k.mid, k.params, k.C, c, p1);
-    rows_load_params<E2>(k.post, k.params, k.C, c, p2);
-
-    const char *inp = static_cast<const char *>(k.in) + (size_t)plane * (size_t)(k.H * k.W) * ES;
-    const int32_t col0 = j * VEC;            // first level-0 column of the lane's block
-    const int32_t c1s = j * VB - PW2;        // first level-1 column the lane computes
-    bool lin[NL > 0 ? NL : 1], xin[NX > 0 ? NX : 1], c1in[NC1];
-#pragma unroll
-    for (int n = 0; n < NL; ++n) lin[n] = col0 - NL + n >= 0;
-#pragma unroll
-    for (int n = 0; n < NX; ++n) xin[n] = col0 + VEC + n < k.W;
-#pragma unroll
-    for (int n = 0; n < NC1; ++n) c1in[n] = c1s + n >= 0 && c1s + n < k.W1;
-
-    struct RowRaw {
-        Raw<BF16, VEC> v;
-        Raw<BF16, 1> l[NL > 0 ? NL : 1], x[NX > 0 ? NX : 1];
-        bool ok;
-    };
-    // issue the loads of input row ih (clamped to a safe address when the row is padding)
-    auto fetch = [&](int32_t ih, RowRaw &r) {
-        r.ok = ih >= 0 && ih < k.H;
-        const uint32_t rowoff = r.ok ? (uint32_t)(ih * k.W) : 0u;
-        r.v = load_raw<BF16, VEC>(inp, rowoff + (uint32_t)col0);
-#pragma unroll
-        for (int n = 0; n < NL; ++n) r.l[n] = load_raw<BF16, 1>(inp, lin[n] ? rowoff + (uint32_t)(col0 - NL + n) : 0u);
-#pragma unroll
-        for (int n = 0; n < NX; ++n) r.x[n] = load_raw<BF16, 1>(inp, xin[n] ? rowoff + (uint32_t)(col0 + VEC + n) : 0u);
-    };
-    // registers -> level-0 row: leading element-wise operations, then the first pool's padding
-    auto settle = [&](const RowRaw &r, float (&w)[NC0]) {
-        float xv[VEC];
-        unpack<BF16, VEC>(r.v, xv);
-#pragma unroll
-        for (int n = 0; n < VEC; ++n) w[NL + n] = xv[n];
-#pragma unroll
-        for (int n = 0; n < NL; ++n) {
-            float one[1];
-            unpack<BF16, 1>(r.l[n], one);
-            w[n] = one[0];
-        }
-#pragma unroll
-        for (int n = 0; n < NX; ++n) {
-            float one[1];
-            unpack<BF16, 1>(r.x[n], one);
-            w[NL + VEC + n] = one[0];
-        }
-        rows_apply<BF16, E0, NC0>(w, p0);
-#pragma unroll
-        for (int n = 0; n < NL; ++n) w[n] = (r.ok && lin[n]) ? w[n] : pad0;
-#pragma unroll
-        for (int n = 0; n < VEC; ++n) w[NL + n] = r.ok ? w[NL + n] : pad0;
-#pragma unroll
-        for (int n = 0; n < NX; ++n) w[NL + VEC + n] = (r.ok && xin[n]) ? w[NL + VEC + n] : pad0;
-    };
-    // level-1 row r1 from the kh1 level-0 rows w0[0..KH1): first pool, middle element-wise
-    // operations, then the second pool's padding
-    auto level1 = [&](int32_t r1, const float (*w0)[NC0], float (&y)[NC1]) {
-        const int32_t hw = r1 * SH1 - PH1;
-#pragma unroll
-        for (int n = 0; n < NC1; ++n) {
-            if (MAX1) {
-                float best = -INFINITY;
-#pragma unroll
-                for (int dh = 0; dh < KH1; ++dh)
-#pragma unroll
-                    for (int dw = 0; dw < KW1; ++dw) best = __builtin_fmaxf(best, w0[dh][n * SW1 + dw]);
-                y[n] = best;
-            } else {
-                float sum = 0.0f;
-#pragma unroll
-                for (int dh = 0; dh < KH1; ++dh)
-#pragma unroll
-                    for (int dw = 0; dw < KW1; ++dw) sum = sum + w0[dh][n * SW1 + dw];
-                float inv = k.pool1.inv_kk;
-                if (!k.pool1.count_include_pad) {
-                    const int32_t w0c = (c1s + n) * SW1 - PW1;
-                    const int32_t nr_ = min(hw + KH1, k.H) - max(hw, 0);
-                    const int32_t nc_ = min(w0c + KW1, k.W) - max(w0c, 0);
-                    inv = 1.0f / (float)max(nr_ * nc_, 1);
-                }
-                y[n] = round_store<BF16>(sum * inv);
-            }
-        }
-        rows_apply<BF16, E1, NC1>(y, p1);
-        const bool rok = r1 >= 0 && r1 < k.H1;
-#pragma unroll
-        for (int n = 0; n < NC1; ++n) y[n] = (rok && c1in[n]) ? y[n] : pad1;
-    };
-
-    const int32_t oh0 = chunk * k.rc;
-    const int32_t oh1 = live ? min(k.Ho, oh0 + k.rc) : oh0;
-    const int32_t ow0 = j * VO;
-    const bool vec_store = (k.Wo % VO) == 0 && ow0 + VO <= k.Wo;
-    const uint32_t oplane = plane * (uint32_t)(k.Ho * k.Wo);
-
-    float keep0[KEEP0 > 0 ? KEEP0 : 1][NC0];  // newest level-0 rows, shared with the next level-1 row
-    float win1[KH2][NC1];                     // level-1 rows under the current output row
-    {
-        const int32_t r1f = oh0 * SH2 - PH2;   // first level-1 row of the first output row
-        const int32_t h0f = r1f * SH1 - PH1;   // first level-0 row under it
-        RowRaw r[R0];
-#pragma unroll
-        for (int w = 0; w < R0; ++w) fetch(h0f + w, r[w]);
-        float l0[R0][NC0];
-#pragma unroll
-        for (int w = 0; w < R0; ++w) settle(r[w], l0[w]);
-#pragma unroll
-        for (int a = 0; a < KH2; ++a) level1(r1f + a, &l0[a * SH1], win1[a]);
-#pragma unroll
-        for (int w = 0; w < KEEP0; ++w)
-#pragma unroll
-            for (int n = 0; n < NC0; ++n) keep0[w][n] = l0[R0 - KEEP0 + w][n];
-    }
-    for (int32_t oh = oh0; oh < oh1; ++oh) {
-        const int32_t r1w = oh * SH2 - PH2;              // first level-1 row of this output row's windows
-        const int32_t r1n = r1w + KH2;                   // first new level-1 row of the next output row
-        const int32_t h0n = (r1n - 1) * SH1 - PH1 + KH1;  // first new level-0 row of the next output row
-        RowRaw nr[NS0];
-        const bool more = oh + 1 < oh1;
-        if (more) {
-#pragma unroll
-            for (int n = 0; n < NS0; ++n) fetch(h0n + n, nr[n]);
-        }
-
-        float y[VO];
-        int32_t yi[VO];
-#pragma unroll
-        for (int e = 0; e < VO; ++e) {
-            const int32_t w0 = c1s + e * SW2;  // first level-1 column of this output's window
-            if (MAX2) {
-                float best = -INFINITY;
-                int32_t bi = max(r1w, 0) * k.W1 + max(w0, 0);  // first in-range cell
-#pragma unroll
-                for (int dh = 0; dh < KH2; ++dh)
-#pragma unroll
-                    for (int dw = 0; dw < KW2; ++dw) {
-                        const float v = win1[dh][e * SW2 + dw];
-                        if constexpr (WANT_IDX) {
-                            const bool g = v > best;
-                            best = g ? v : best;
-                            bi = g ? (r1w + dh) * k.W1 + w0 + dw : bi;
-                        } else {
-                            best = __builtin_fmaxf(best, v);
-                        }
-                    }
-                y[e] = best;
-                yi[e] = bi;
-            } else {
-                float sum = 0.0f;
-#pragma unroll
-                for (int dh = 0; dh < KH2; ++dh)
-#pragma unroll
-                    for (int dw = 0; dw < KW2; ++dw) sum = sum + win1[dh][e * SW2 + dw];
-                float inv = k.pool2.inv_kk;
-                if (!k.pool2.count_include_pad) {
-                    const int32_t nr_ = min(r1w + KH2, k.H1) - max(r1w, 0);
-                    const int32_t nc_ = min(w0 + KW2, k.W1) - max(w0, 0);
-                    inv = 1.0f / (float)max(nr_ * nc_, 1);
-                }
-                y[e] = round_store<BF16>(sum * inv);
-                yi[e] = 0;
-            }
-        }
-        rows_apply<BF16, E2, VO>(y, p2);
-        {
-            const uint32_t ooff = oplane + (uint32_t)(oh * k.Wo + ow0);
-            if (vec_store) {
-                store_elems<BF16, VO>(k.out, ooff, y);
-                if constexpr (WANT_IDX) {
-                    if (k.idx) {
-#pragma unroll
-                        for (int e = 0; e < VO; ++e) k.idx[ooff + e] = yi[e];
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < VO; ++e)
-                    if (ow0 + e < k.Wo) {
-                        const float one[1] = {y[e]};
-                        store_elems<BF16, 1>(k.out, ooff + e, one);
-                        if constexpr (WANT_IDX) {
-                            if (k.idx) k.idx[ooff + e] = yi[e];
-                        }
-                    }
-            }
-        }
-        // slide both windows down to the next output row
-#pragma unroll
-        for (int w = 0; w < KEEP1; ++w)
-#pragma unroll
-            for (int n = 0; n < NC1; ++n) win1[w][n] = win1[w + SH2][n];
-        if (more) {
-            float l0[KEEP0 + NS0][NC0];
-#pragma unroll
-            for (int w = 0; w < KEEP0; ++w)
-#pragma unroll
-                for (int n = 0; n < NC0; ++n) l0[w][n] = keep0[w][n];
-#pragma unroll
-            for (int n = 0; n < NS0; ++n) settle(nr[n], l0[KEEP0 + n]);
-#pragma unroll
-            for (int a = 0; a < SH2; ++a) level1(r1n + a, &l0[a * SH1], win1[KEEP1 + a]);
-#pragma unroll
-            for (int w = 0; w < KEEP0; ++w)
-#pragma unroll
-                for (int n = 0; n < NC0; ++n) keep0[w][n] = l0[NS0 + w][n];
-        }
-    }
-}
 
 // =============================================================================
 // Signature table, applicability test and launcher.
@@ -289,6 +31,34 @@ bool rows2_supported(const PoolRows2K &k)
         return rows_pool_is<decltype(s1)>(k.pool1) && rows_pool_is<decltype(s2)>(k.pool2) && c0 == decltype(e0)::value &&
                c1 == decltype(e1)::value && c2 == decltype(e2)::value;
     });
+}
+
+// Can pool_rows2_kernel be instantiated for these shapes (see its static_assert), with
+// register windows of a reasonable size?
+bool rows2_buildable(const PoolRows2K &k, int32_t vec)
+{
+    if (rows_ew_code(k.pre, k.n_pre) < 0 || rows_ew_code(k.mid, k.n_mid) < 0 || rows_ew_code(k.post, k.n_post) < 0)
+        return false;
+    const PoolK &a = k.pool1, &b = k.pool2;
+    if (a.sw < 1 || b.sw < 1 || vec % (a.sw * b.sw) != 0 || a.kh < a.sh || b.kh < b.sh) return false;
+    const int32_t vo = vec / (a.sw * b.sw);
+    const int32_t nc1 = (vo - 1) * b.sw + b.kw, nl = b.pw * a.sw + a.pw, nc0 = (nc1 - 1) * a.sw + a.kw;
+    if (nc0 - nl - vec < 0) return false;
+    const int32_t r0 = (b.kh - 1) * a.sh + a.kh;
+    return r0 * nc0 + b.kh * nc1 <= 160;
+}
+
+std::string rows2_expr(const PoolRows2K &k, bool bf16, bool want_idx)
+{
+    char b[400];
+    const PoolK &p = k.pool1, &q = k.pool2;
+    std::snprintf(b, sizeof b,
+                  "bs::pool_rows2_kernel<%s, bs::RowsSpec<%d, %d, %d, %d, %d, %d, %d>, "
+                  "bs::RowsSpec<%d, %d, %d, %d, %d, %d, %d>, %d, %d, %d, %s>",
+                  bf16 ? "true, 8" : "false, 4", p.kind, p.kh, p.kw, p.sh, p.sw, p.ph, p.pw, q.kind, q.kh, q.kw, q.sh,
+                  q.sw, q.ph, q.pw, rows_ew_code(k.pre, k.n_pre), rows_ew_code(k.mid, k.n_mid),
+                  rows_ew_code(k.post, k.n_post), want_idx ? "true" : "false");
+    return b;
 }
 
 template <bool BF16, int VEC>

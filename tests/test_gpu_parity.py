@@ -38,15 +38,25 @@ def run_gpu(layers, x, res, dtype, **opts):
 
 
 def check(layers, x, res, dtype, label, **opts):
-    print(f"[parity] {label} shape={x.shape} dtype={dtype} opts={opts}", flush=True)
+    """One stack through the HIP path against the oracle.  When the plan uses kernels built at
+    plan time for the stack's signature, the same stack is checked again with such builds
+    switched off (the kernels that read shapes at run time), so both paths stay covered."""
     ref, ref_idx, _ = bf.run_stack(layers, x, res, dtype)
+    info = _check_one(layers, x, res, dtype, label, ref, ref_idx, **opts)
+    if "jit" not in opts and any(q["run_time_build"] for q in info["sequences"]):
+        _check_one(layers, x, res, dtype, label + "/no-run-time-build", ref, ref_idx, jit=-1, **opts)
+    return info
+
+
+def _check_one(layers, x, res, dtype, label, ref, ref_idx, **opts):
+    print(f"[parity] {label} shape={x.shape} dtype={dtype} opts={opts}", flush=True)
     out, idx, info = run_gpu(layers, x, res, dtype, **opts)
     assert out.shape == ref.shape
     scale = float(np.abs(ref).max()) or 1.0
     err = float(np.abs(out - ref).max())
     ndiff = int((out.view(np.uint32) != ref.view(np.uint32)).sum())
     print(f"         max|err|={err:.3e} (bar {TOL[dtype] * scale:.3e}) non-identical={ndiff} "
-          f"variants={[q['variant_name'] for q in info['sequences']]}", flush=True)
+          f"variants={[q['variant_name'] + ('*' if q['run_time_build'] else '') for q in info['sequences']]}", flush=True)
     assert err <= TOL[dtype] * scale, label
     assert len(idx) == len(ref_idx)
     for k, (a, b) in enumerate(zip(idx, ref_idx)):
@@ -295,6 +305,36 @@ def test_pool_rows2_kernel(shape, dtype):
             assert info["sequences"][0]["variant_name"] == "pool_rows", name
         info = check(layers, x, [], dtype, f"rows2/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
         assert [q["variant_name"] for q in info["sequences"]] == ["lds_tile"] * info["n_sequences"]
+
+
+# ------------------------------------------------------------------ run-time builds
+def _built_stacks(c):
+    """Signatures with no instance compiled into the library."""
+    return {
+        "max5s1p2": ([wl.maxpool(5, 1, 2, True), wl.bn_params(c, 80), wl.relu()], 0),
+        "avg2s1p0": ([wl.relu(), wl.avgpool(2, 1, 0)], 0),
+        "max3x2": ([wl.bn_params(c, 81), wl.maxpool((3, 2), (1, 2), (1, 0), True)], 0),
+        "three_levels": ([wl.maxpool(3, 2, 1), wl.bn_params(c, 82), wl.relu(), wl.avgpool(2, 2, 0),
+                          wl.maxpool(3, 1, 1, True)], 0),
+        "listing2": ([wl.maxpool(3, 1, 1), wl.bn_params(c, 83), wl.relu(), wl.avgpool(2, 2, 0)], 0),
+        "residual": ([wl.bn_params(c, 84), wl.add(), wl.relu(), wl.maxpool(3, 2, 1, True), wl.bn_params(c, 85),
+                      wl.relu(), wl.avgpool(3, 1, 1, False)], 1),
+        "two_max": ([wl.maxpool(3, 1, 1, True), wl.relu(), wl.maxpool(3, 2, 0, True)], 0),
+    }
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 24, 32), (1, 2, 31, 30), (2, 4, 17, 16)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_run_time_builds(shape, dtype):
+    """Stacks whose signature has no pre-compiled kernel get one built at plan time (required
+    here: a failed build fails the plan); the result matches the oracle, and so does the same
+    stack on the kernels that read shapes at run time."""
+    for name, (layers, n_res) in _built_stacks(shape[1]).items():
+        x = wl.activation(shape, 72, dtype)
+        res = [wl.activation(shape, 73 + i, dtype) for i in range(n_res)]
+        info = check(layers, x, res, dtype, f"built/{name}{shape}", jit=1)
+        assert any(q["run_time_build"] for q in info["sequences"]), name
+        check(layers, x, res, dtype, f"built/{name}{shape}/off", jit=-1)
 
 
 # ------------------------------------------------------------------ special values

@@ -26,12 +26,42 @@ def test_listing2_example_partition():
     assert info["operations"] == ["MaxPooling", "BatchNorm", "ReLU", "AvgPooling", "AvgNormalization"]
     assert steps_of(info) == [(0, 3), (3, 2)]
     assert [s["pool_operation"] for s in info["steps"]] == [0, 3]
-    # both steps fit one sequence (Listing 2's sequence_0); the automatic plan keeps them apart
-    # only because the first step alone has a pre-compiled fast kernel and the pair has none
+    # both steps fit one sequence (Listing 2's sequence_0), whose kernel is built for this
+    # signature when the stack is planned ...
+    assert info["n_sequences"] == 1 and info["workspace_bytes"] == 0
+    assert info["sequences"][0]["run_time_build"] == 1 and info["sequences"][0]["variant_name"] == "pool_rows"
     one = plan(layers, (1, 4, 16, 16), force_variant=bs.BS_VARIANT_LDS_TILE)
     assert one["n_sequences"] == 1 and one["workspace_bytes"] == 0
     assert steps_of(one) == [(0, 3), (3, 2)]
-    assert info["n_sequences"] == 2 and info["workspace_bytes"] > 0
+    # ... and without run-time builds the plan keeps the steps apart, because each step alone
+    # has a pre-compiled fast kernel and the pair would run the slow run-time-shape kernel
+    two = plan(layers, (1, 4, 16, 16), jit=-1)
+    assert two["n_sequences"] == 2 and two["workspace_bytes"] > 0
+    assert [q["run_time_build"] for q in two["sequences"]] == [0, 0]
+
+
+def test_run_time_builds_compile_without_a_device():
+    """Signatures with no pre-compiled kernel are marked for a run-time build by a host-only
+    plan, and those builds compile for gfx950 on a machine without a GPU."""
+    cases = [
+        ([wl.maxpool(5, 1, 2, True), wl.bn_params(4, 0), wl.relu()], (2, 4, 32, 32), ["pool_rows"], 2),
+        ([wl.maxpool(3, 2, 1), wl.bn_params(4, 1), wl.relu(), wl.avgpool(2, 2), wl.maxpool(3, 1, 1)],
+         (2, 4, 64, 64), ["lds_tile"], 1),
+        ([wl.bn_params(4, 2), wl.add(), wl.relu(), wl.maxpool(3, 2, 1)], (1, 4, 30, 30), ["lds_tile"], 1),
+    ]
+    for dt in ("f32", "bf16"):
+        for layers, shape, variants, n_kernels in cases:
+            st = bs.Stack(layers, shape, dt).plan(host_only=1, num_cus=256)
+            info = st.info()
+            assert [q["variant_name"] for q in info["sequences"]] == variants
+            assert all(q["run_time_build"] == 1 for q in info["sequences"])
+            assert bs.bs_stack_jit_check(st.handle) == n_kernels  # with and without index outputs
+            st.close()
+    # the BASELINE stacks need none
+    layers, shape, _ = wl.build("vgg_a")
+    st = bs.Stack(layers, shape, "f32").plan(host_only=1, num_cus=256)
+    assert bs.bs_stack_jit_check(st.handle) == 0
+    st.close()
 
 
 def test_step_rule_elementwise_always_joins_second_pool_opens_a_step():
