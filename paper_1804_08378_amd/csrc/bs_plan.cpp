@@ -425,6 +425,16 @@ static bool jit_allowed(const bs_stack *s)
     return s->opts.jit >= 0 && !s->jit_failed && jit_enabled();
 }
 
+// A lane of the register sliding-window kernels computes (and, beyond its own 128-bit block,
+// loads with scalar loads) every input column its windows touch: nc0 columns for vec owned.
+// Measured on MI355X, once that ratio passes 1.75 (5x5 windows, or a 3x3 stride-1 pool behind
+// another pool) the LDS kernels, which share those columns between lanes, are faster --
+// provided the sequence gets a specialised LDS build rather than the run-time-shape kernel.
+static bool rows_columns_pay(const bs_stack *s, int32_t nc0, int32_t vec)
+{
+    return nc0 * 4 <= vec * 7 || !jit_allowed(s) || s->opts.force_variant == BS_VARIANT_POOL_ROWS;
+}
+
 // Two consecutive pooling operations, BatchNorm and ReLU only around them, no index output on
 // the first, in shapes the two-level rows kernel is instantiated for (or can be built for).
 static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
@@ -459,6 +469,10 @@ static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
     // every output column must fall under some lane's column block
     const int32_t sws = k.pool1.sw * k.pool2.sw;
     if (vec % sws != 0 || (int64_t)(k.W / vec) * (vec / sws) < k.Wo) return false;
+    {
+        const int32_t nc1 = (vec / sws - 1) * k.pool2.sw + k.pool2.kw;
+        if (!rows_columns_pay(s, (nc1 - 1) * k.pool1.sw + k.pool1.kw, vec)) return false;
+    }
     if (fill) fill->rows2 = k;
     return true;
 }
@@ -494,6 +508,7 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
         return false;
     // every output column must fall under some lane's column block
     if ((int64_t)(k.W / vec) * (vec / k.pool.sw) < k.Wo) return false;
+    if (!rows_columns_pay(s, vec + k.pool.kw - k.pool.sw, vec)) return false;
     if (fill) fill->rows = k;
     return true;
 }

@@ -300,7 +300,8 @@ def test_pool_rows2_kernel(shape, dtype):
     for name, layers in _rows2_stacks(shape[1]).items():
         x = wl.activation(shape, 71, dtype)
         for rc in (0, 1, 3, 1000):
-            info = check(layers, x, [], dtype, f"rows2/{name}{shape}/rc{rc}", tile_rows=rc)
+            info = check(layers, x, [], dtype, f"rows2/{name}{shape}/rc{rc}", tile_rows=rc,
+                         force_variant=bs.BS_VARIANT_POOL_ROWS)
             assert info["n_sequences"] == 1, name
             assert info["sequences"][0]["variant_name"] == "pool_rows", name
         info = check(layers, x, [], dtype, f"rows2/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
