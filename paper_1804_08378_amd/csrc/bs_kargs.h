@@ -41,6 +41,7 @@ constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
 constexpr int K_STREAM_U = 4;     // 128-bit vectors per lane in stream_kernel
 constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
+constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
 
 // n / d for 0 <= n < 2^31 by multiply-high and shift.

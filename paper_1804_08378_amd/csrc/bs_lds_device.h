@@ -270,6 +270,100 @@ BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t vo, i
     }
 }
 
+// RB consecutive output rows of one strip (static shapes): the kh input rows of the current
+// windows stay in registers and slide down by sh rows per output row, so an input row is read
+// from LDS once per block instead of once per output row it contributes to.  Without index
+// outputs a max is taken column-wise first and then across each window (same value: max is
+// exact and order-free for the finite inputs the library accepts).
+//   src      16-byte aligned LDS address of the first window row of the block
+//   nrows    output rows wanted (1..RB); rows beyond are neither read nor emitted
+//   h0, w0   global row / column of the first window's first cell in the input plane
+//   emit(i, val, bidx)  receives output row i of the block
+template <class P, int VO, int D, bool WANT_IDX, int RB, class F>
+BS_DEV void pool_block(const P &p, const float *src, int32_t pitch, int32_t nrows, int32_t h0, int32_t w0,
+                       int32_t Hp, int32_t Wp, F &&emit)
+{
+    constexpr int KH = P::kh(), KW = P::kw(), SH = P::sh(), SW = P::sw();
+    constexpr int NC = (VO - 1) * SW + KW;                    // columns the windows span
+    constexpr int NR = D == 0 ? NC : (D + NC + 3) / 4 * 4;    // floats read per row
+    constexpr int KEEP = KH > SH ? KH - SH : 0;               // rows two consecutive windows share
+    constexpr bool IS_MAX = P::kind() == OP_MAXPOOL;
+    float w[KH][NR];
+#pragma unroll
+    for (int dh = 0; dh < KH; ++dh) lds_read_row<NR>(src + dh * pitch, w[dh]);
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        if (i < nrows) {
+            const int32_t hi = h0 + i * SH;
+            float val[VO];
+            int32_t bidx[VO];
+            if constexpr (IS_MAX && !WANT_IDX) {
+                float cm[NC];
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    cm[c] = w[0][D + c];
+#pragma unroll
+                    for (int dh = 1; dh < KH; ++dh) cm[c] = __builtin_fmaxf(cm[c], w[dh][D + c]);
+                }
+#pragma unroll
+                for (int e = 0; e < VO; ++e) {
+                    val[e] = cm[e * SW];
+#pragma unroll
+                    for (int dw = 1; dw < KW; ++dw) val[e] = __builtin_fmaxf(val[e], cm[e * SW + dw]);
+                    bidx[e] = 0;
+                }
+            } else if constexpr (IS_MAX) {
+#pragma unroll
+                for (int e = 0; e < VO; ++e) {
+                    float best = -INFINITY;
+                    int32_t bi = max(hi, 0) * Wp + max(w0 + e * SW, 0);  // first in-range cell
+#pragma unroll
+                    for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                        for (int dw = 0; dw < KW; ++dw) {
+                            const float v = w[dh][D + e * SW + dw];
+                            const bool g = v > best;
+                            best = g ? v : best;
+                            bi = g ? (hi + dh) * Wp + w0 + e * SW + dw : bi;
+                        }
+                    val[e] = best;
+                    bidx[e] = bi;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < VO; ++e) {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                        for (int dw = 0; dw < KW; ++dw) sum = sum + w[dh][D + e * SW + dw];
+                    if (p.cip()) {
+                        val[e] = sum * p.inv_kk();
+                    } else {
+                        const int32_t we = w0 + e * SW;
+                        const int32_t nr = min(hi + KH, Hp) - max(hi, 0);
+                        const int32_t nc = min(we + KW, Wp) - max(we, 0);
+                        // windows wholly outside the plane can make nr * nc <= 0; such outputs are never stored
+                        val[e] = sum * (1.0f / (float)max(nr * nc, 1));
+                    }
+                    bidx[e] = 0;
+                }
+            }
+            emit(i, val, bidx);
+        }
+        if (i + 1 < RB) {
+#pragma unroll
+            for (int dh = 0; dh < KEEP; ++dh)
+#pragma unroll
+                for (int n = 0; n < NR; ++n) w[dh][n] = w[dh + SH][n];
+            if (i + 1 < nrows) {
+#pragma unroll
+                for (int dh = KEEP; dh < KH; ++dh) lds_read_row<NR>(src + ((i + 1) * SH + dh) * pitch, w[dh]);
+            }
+        }
+    }
+}
+
 // What a work-group knows about its tile.
 struct TileCtx {
     int32_t ti, tj, plane0, nplanes;
@@ -392,15 +486,9 @@ BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, con
 #pragma unroll
             for (int e = 0; e < VO; ++e) cin[e] = e < vo && gc + e >= 0 && gc + e < lv.W;
             const bool strip_vec = P::is_static && cx.vec_store_ok && gc >= 0 && gc + VO - 1 < cx.end_c;
-            for (int32_t r = (int32_t)ty; r < lv.rows; r += lv.rt) {
+            // what happens to the VO outputs of rectangle row r once they are pooled
+            auto finish = [&](int32_t r, float (&val)[VO], int32_t (&bi)[VO]) {
                 const int32_t gr = cx.r0 + r;
-                const int32_t h0 = gr * p.sh() - p.ph();
-                float val[VO];
-                int32_t bi[VO];
-#pragma unroll
-                for (int e = 0; e < VO; ++e) bi[e] = 0;
-                pool_strip<P, VO, D, WANT_IDX>(p, splane + (r * p.sh()) * pv.pitch + scol, d_rt, vo, pv.pitch, h0,
-                                               w0, pv.H, pv.W, val, bi);
                 if (p.kind() != OP_MAXPOOL) {
 #pragma unroll
                     for (int e = 0; e < VO; ++e) val[e] = round_store<BF16>(val[e]);
@@ -447,6 +535,29 @@ BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, con
                         for (int e = 0; e < VO; ++e)
                             if (e < vo) d[e] = w[e];
                     }
+                }
+            };
+            if constexpr (P::is_static) {
+                // lanes of the ct x rt grid take blocks of K_LDS_RB consecutive rows
+                constexpr int RB = K_LDS_RB;
+                const int32_t nblk = (lv.rows + RB - 1) / RB;
+                for (int32_t b = (int32_t)ty; b < nblk; b += lv.rt) {
+                    const int32_t rb0 = b * RB;
+                    pool_block<P, VO, D, WANT_IDX, RB>(
+                        p, splane + (rb0 * P::sh()) * pv.pitch + scol, pv.pitch, min(RB, lv.rows - rb0),
+                        (cx.r0 + rb0) * P::sh() - P::ph(), w0, pv.H, pv.W,
+                        [&](int i, float (&val)[VO], int32_t (&bi)[VO]) { finish(rb0 + i, val, bi); });
+                }
+            } else {
+                for (int32_t r = (int32_t)ty; r < lv.rows; r += lv.rt) {
+                    const int32_t h0 = (cx.r0 + r) * p.sh() - p.ph();
+                    float val[VO];
+                    int32_t bi[VO];
+#pragma unroll
+                    for (int e = 0; e < VO; ++e) bi[e] = 0;
+                    pool_strip<P, VO, D, WANT_IDX>(p, splane + (r * p.sh()) * pv.pitch + scol, d_rt, vo, pv.pitch, h0,
+                                                   w0, pv.H, pv.W, val, bi);
+                    finish(r, val, bi);
                 }
             }
         }

@@ -419,6 +419,9 @@ static void plan_direct(const bs_stack *s, Sequence &q)
     q.n_levels = 1;
 }
 
+constexpr int32_t K_AUTO_STEPS = 5;                  // steps per sequence of an unrestricted automatic plan
+constexpr uint64_t K_DEFAULT_LDS_BYTES = 64 * 1024;  // on-chip budget per work-group when the caller gives none
+
 // May this plan rely on run-time kernel builds for signatures without a pre-compiled instance?
 static bool jit_allowed(const bs_stack *s)
 {
@@ -875,49 +878,73 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
     s->seqs.clear();
     const int32_t threads = o.threads_per_group > 0 ? o.threads_per_group : 256;
     const bool per_layer = o.breadth_first != 0;
-    std::vector<SeqDraft> drafts;
-    SeqDraft cur{0, 0};
     auto range_ops = [&](const SeqDraft &d, int32_t &first_op, int32_t &n_ops) {
         first_op = s->steps[d.first_step].first_op;
         const Step &lst = s->steps[d.first_step + d.n_steps - 1];
         n_ops = lst.first_op + lst.n_ops - first_op;
     };
-    for (int32_t i = 0; i < (int32_t)s->steps.size(); ++i) {
-        if (cur.n_steps == 0) {
-            cur = SeqDraft{i, 1};
-        } else {
-            SeqDraft trial{cur.first_step, cur.n_steps + 1};
-            int32_t fo, no;
-            range_ops(trial, fo, no);
-            bool fits = !per_layer;
-            if (fits && o.max_steps_per_sequence > 0 && trial.n_steps > o.max_steps_per_sequence) fits = false;
-            if (fits && !seq_capacity_ok(s, fo, no, true)) fits = false;
-            if (fits && seq_min_lds(s, fo, no, threads) > lim.max_lds_bytes) fits = false;
-            // cost rule: do not trade a sequence that has a pre-compiled fast kernel for a longer
-            // one that would run the much slower run-time-shape build
-            if (fits && o.force_variant == BS_VARIANT_AUTO) {
-                int32_t co, cn;
-                range_ops(cur, co, cn);
-                if (seq_is_fast(s, co, cn) && !seq_is_fast(s, fo, no)) fits = false;
-            }
-            if (fits) {
-                cur = trial;
-            } else {
-                drafts.push_back(cur);
+    // greedy fill (Section 4.1): append steps while the sequence fits; `cap` = most steps per sequence
+    auto fill = [&](int32_t cap, std::vector<SeqDraft> &drafts) -> bs_status {
+        drafts.clear();
+        SeqDraft cur{0, 0};
+        for (int32_t i = 0; i < (int32_t)s->steps.size(); ++i) {
+            if (cur.n_steps == 0) {
                 cur = SeqDraft{i, 1};
+            } else {
+                SeqDraft trial{cur.first_step, cur.n_steps + 1};
+                int32_t fo, no;
+                range_ops(trial, fo, no);
+                bool fits = !per_layer;
+                if (fits && cap > 0 && trial.n_steps > cap) fits = false;
+                if (fits && !seq_capacity_ok(s, fo, no, true)) fits = false;
+                if (fits && seq_min_lds(s, fo, no, threads) > lim.max_lds_bytes) fits = false;
+                // cost rule: do not trade a sequence that has a pre-compiled fast kernel for a
+                // longer one that would run the much slower run-time-shape build
+                if (fits && o.force_variant == BS_VARIANT_AUTO) {
+                    int32_t co, cn;
+                    range_ops(cur, co, cn);
+                    if (seq_is_fast(s, co, cn) && !seq_is_fast(s, fo, no)) fits = false;
+                }
+                if (fits) {
+                    cur = trial;
+                } else {
+                    drafts.push_back(cur);
+                    cur = SeqDraft{i, 1};
+                }
+            }
+            // a single step must be executable on its own
+            if (cur.n_steps == 1) {
+                int32_t fo, no;
+                range_ops(cur, fo, no);
+                if (!seq_capacity_ok(s, fo, no, true)) return BS_ERR_UNSUPPORTED;
+                if (seq_min_lds(s, fo, no, threads) > lim.max_lds_bytes &&
+                    seq_smallest_lds(s, fo, no) > lim.max_lds_bytes)
+                    return BS_ERR_NO_FIT;
             }
         }
-        // a single step must be executable on its own
-        if (cur.n_steps == 1) {
-            int32_t fo, no;
-            range_ops(cur, fo, no);
-            if (!seq_capacity_ok(s, fo, no, true)) return BS_ERR_UNSUPPORTED;
-            if (seq_min_lds(s, fo, no, threads) > lim.max_lds_bytes &&
-                seq_smallest_lds(s, fo, no) > lim.max_lds_bytes)
-                return BS_ERR_NO_FIT;
+        if (cur.n_steps > 0) drafts.push_back(cur);
+        return BS_OK;
+    };
+    std::vector<SeqDraft> drafts;
+    if (o.max_steps_per_sequence > 0 || per_layer || o.force_variant != BS_VARIANT_AUTO) {
+        const bs_status fs = fill(o.max_steps_per_sequence, drafts);
+        if (fs != BS_OK) return fs;
+    } else {
+        // Unrestricted, automatic: every further stacked step adds halo that all earlier levels
+        // recompute (Section 5.1), and the multi-step kernels are bound by arithmetic, not by
+        // memory, once a few steps are fused -- measured on MI355X, four to five steps per
+        // sequence are fastest.  Cap sequences at K_AUTO_STEPS steps, then even out their
+        // lengths (8 steps run as 4 + 4 rather than 5 + 3).
+        bs_status fs = fill(K_AUTO_STEPS, drafts);
+        if (fs != BS_OK) return fs;
+        const int32_t n_seq = (int32_t)drafts.size(), n_steps = (int32_t)s->steps.size();
+        const int32_t even = n_seq > 0 ? (n_steps + n_seq - 1) / n_seq : 0;
+        if (n_seq > 1 && even < K_AUTO_STEPS) {
+            std::vector<SeqDraft> balanced;
+            fs = fill(even, balanced);
+            if (fs == BS_OK && balanced.size() == drafts.size()) drafts.swap(balanced);
         }
     }
-    if (cur.n_steps > 0) drafts.push_back(cur);
 
     const size_t es = dtype_size(s->dtype);
     uint64_t max_inter = 0;
@@ -997,10 +1024,12 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
         if (lim.num_cus == 0) lim.num_cus = dev.num_cus;
     }
     if (lim.num_cus == 0) lim.num_cus = 256;
-    // Default on-chip budget per work-group: a quarter of the 64 KiB a group may address
-    // keeps several groups resident per compute unit (the paper caps shared memory well
-    // below what the device offers for the same reason, Section 4.4).
-    if (lim.max_lds_bytes == 0) lim.max_lds_bytes = 32 * 1024;
+    // Default on-chip budget per work-group: all 64 KiB a group may address.  The paper caps
+    // shared memory well below what its device offers to keep occupancy (Section 4.4); here a
+    // compute unit has 160 KiB, two such groups still fit, and larger tiles (less halo to
+    // recompute) measured faster than more resident groups.  The tile search still prefers
+    // smaller footprints among equally good tiles.
+    if (lim.max_lds_bytes == 0) lim.max_lds_bytes = K_DEFAULT_LDS_BYTES;
 
     stack->opts = o;
     stack->jit_failed = false;

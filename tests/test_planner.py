@@ -95,7 +95,7 @@ def test_baseline_configs_are_one_fused_sequence(name, steps, variant):
         assert q["variant_name"] == variant
         assert tuple(q["in_shape"]) == shape and tuple(q["out_shape"]) == wl.output_shape(layers, shape)
         assert info["algorithmic_bytes"] == wl.algorithmic_bytes(layers, shape, dt)
-        assert q["lds_bytes"] <= 32 * 1024
+        assert q["lds_bytes"] <= 64 * 1024
         assert q["grid"] >= 1
         if name == "halo_stress":
             # four output rows per lane: 2*4 + 3 input rows of every 8 are loaded
