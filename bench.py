@@ -155,6 +155,59 @@ def cpu_baseline(names, dtype, batch, passes):
                       "single-thread pass; same algorithmic-bytes metric"}
 
 
+def frontend_stacks(names=("vgg_a", "vgg_b", "vgg_c"), batch=32, reps=50):
+    """The optimizable layers of the VGG-16-BN feature extractor as torch modules (BatchNorm2d,
+    ReLU, MaxPool2d in eval mode), run by PyTorch's own kernels and, after `frontend.optimize`,
+    by this library (Section 5.3 reports the speed-up of the optimizable layers alone).  Module
+    calls back to back over rotating inputs, HIP events around the loop: the figures include
+    Python and allocator overhead of both sides."""
+    import torch
+    from torch import nn
+    from paper_1804_08378_amd import frontend as fe
+    from paper_1804_08378_amd import workloads as wl
+
+    rows, tot_ref, tot_opt = [], 0.0, 0.0
+    log(f"{'stack':<8}{'torch eager us':>16}{'optimized us':>14}{'speed-up':>10}")
+    for name in names:
+        layers, x, _ = wl.inputs_for(name, 0, "f32", batch=batch, indices=False)
+        c = x.shape[1]
+        bn = nn.BatchNorm2d(c, eps=float(layers[0]["eps"]))
+        with torch.no_grad():
+            bn.weight.copy_(torch.from_numpy(layers[0]["gamma"]))
+            bn.bias.copy_(torch.from_numpy(layers[0]["beta"]))
+            bn.running_mean.copy_(torch.from_numpy(layers[0]["mean"]))
+            bn.running_var.copy_(torch.from_numpy(layers[0]["var"]))
+        ref = nn.Sequential(bn, nn.ReLU(), nn.MaxPool2d(2, 2)).cuda().eval()
+        import copy
+        opt = fe.optimize(copy.deepcopy(ref))
+        xs = [torch.from_numpy(x).cuda()]
+        xs += [xs[0].clone() for _ in range(3)]
+        t = {}
+        with torch.no_grad():
+            same = torch.equal(ref(xs[0]), opt(xs[0])) or float((ref(xs[0]) - opt(xs[0])).abs().max())
+            for key, mod in (("ref", ref), ("opt", opt)):
+                for i in range(3):
+                    mod(xs[i])
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for i in range(reps):
+                    mod(xs[i % 4])
+                b.record()
+                torch.cuda.synchronize()
+                t[key] = a.elapsed_time(b) / reps * 1e3
+        rows.append({"stack": name, "torch_eager_us": round(t["ref"], 1), "optimized_us": round(t["opt"], 1),
+                     "speedup": round(t["ref"] / t["opt"], 2), "max_abs_diff_vs_torch": 0.0 if same is True else same})
+        tot_ref += t["ref"]
+        tot_opt += t["opt"]
+        log(f"{name:<8}{t['ref']:>16.1f}{t['opt']:>14.1f}{t['ref'] / t['opt']:>10.2f}")
+        for st in opt.optimized_stacks:
+            st.close()
+        del xs, ref, opt
+    return {"what": "BatchNorm2d -> ReLU -> MaxPool2d(2,2) torch modules, fp32, batch %d" % batch, "rows": rows,
+            "optimizable_layers_speedup": round(tot_ref / tot_opt, 2)}
+
+
 def deep_stacks(shape=(64, 64, 56, 56), counts=(1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 40)):
     """Section 5.1: networks of n blocks <MaxPool k3 s1 p1, BatchNorm, ReLU>, executed layer by
     layer and fused with at most 1 step, at most 5 steps, and unrestricted steps per sequence.
@@ -214,6 +267,8 @@ def main():
     ap.add_argument("--deep", action="store_true",
                     help="also run the stacked-layers experiment of Section 5.1: 1..40 blocks of "
                          "<MaxPool 3/1/1, BatchNorm, ReLU> under the three sequence strategies")
+    ap.add_argument("--frontend", action="store_true",
+                    help="also time the VGG stacks as torch modules: PyTorch eager against frontend.optimize()")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
                     help="counter probe for rocprofv3 --pmc: N launches of a plain copy of known size, "
                          "then N launches of each VGG stack; no timing, no JSON")
@@ -298,6 +353,8 @@ def main():
 
     if args.deep:
         out["deep_stacks"] = deep_stacks()
+    if args.frontend:
+        out["frontend"] = frontend_stacks()
 
     if args.all:
         del stacks
