@@ -44,13 +44,13 @@ def run_stack(layers, x, residuals=(), dtype: str = "f32", keep_intermediates: b
             cur = L.add(cur, res.pop(0))
         elif kind == "maxpool":
             if layer.get("return_indices"):
-                cur, idx = L.maxpool(cur, layer["k"], layer["s"], layer["p"], True)
+                cur, idx = L.maxpool(cur, layer["k"], layer["s"], layer["p"], True, layer.get("ceil_mode", False))
                 indices.append(idx)
             else:
-                cur = L.maxpool(cur, layer["k"], layer["s"], layer["p"])
+                cur = L.maxpool(cur, layer["k"], layer["s"], layer["p"], False, layer.get("ceil_mode", False))
         elif kind == "avgpool":
             cur = L.avgpool(cur, layer["k"], layer["s"], layer["p"],
-                            layer.get("count_include_pad", True))
+                            layer.get("count_include_pad", True), layer.get("ceil_mode", False))
         else:
             raise ValueError(f"unknown layer kind {kind!r}")
         if dtype == "bf16":

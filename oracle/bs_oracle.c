@@ -114,10 +114,16 @@ BSO_API void bso_add(const float *a, const float *r, float *y, int64_t n)
     for (int64_t i = 0; i < n; ++i) y[i] = a[i] + r[i];
 }
 
-/* Floor-mode pooling output size. */
-BSO_API int64_t bso_pool_out(int64_t in, int64_t k, int64_t s, int64_t p)
+/* Pooling output size.  Floor mode: the windows that fit the padded input.  Ceil mode (the
+ * rule of the framework the paper's front-end targets; the paper itself is silent): one more
+ * window if the last fitting one leaves cells uncovered, unless that window would start
+ * beyond the input and its leading padding. */
+BSO_API int64_t bso_pool_out(int64_t in, int64_t k, int64_t s, int64_t p, int ceil_mode)
 {
-    return (in + 2 * p - k) / s + 1;
+    if (!ceil_mode) return (in + 2 * p - k) / s + 1;
+    int64_t o = (in + 2 * p - k + s - 1) / s + 1;
+    if ((o - 1) * s >= in + p) --o;
+    return o;
 }
 
 /* ------------------------------------------------------------------ */
@@ -128,9 +134,9 @@ BSO_API int64_t bso_pool_out(int64_t in, int64_t k, int64_t s, int64_t p)
 /* ------------------------------------------------------------------ */
 BSO_API void bso_maxpool(const float *x, float *y, int32_t *idx, int64_t N, int64_t C, int64_t H,
                          int64_t W, int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph,
-                         int64_t pw)
+                         int64_t pw, int ceil_mode)
 {
-    const int64_t Ho = bso_pool_out(H, kh, sh, ph), Wo = bso_pool_out(W, kw, sw, pw);
+    const int64_t Ho = bso_pool_out(H, kh, sh, ph, ceil_mode), Wo = bso_pool_out(W, kw, sw, pw, ceil_mode);
 #pragma omp parallel for schedule(static)
     for (int64_t plane = 0; plane < N * C; ++plane) {
         const float *xp = x + plane * H * W;
@@ -161,14 +167,16 @@ BSO_API void bso_maxpool(const float *x, float *y, int32_t *idx, int64_t N, int6
 /* element-wise "AvgNormalization" (Listing 2).  The sum runs over the */
 /* in-range cells in row-major order starting from +0; padding cells   */
 /* add nothing.  The normalisation multiplies by the float32           */
-/* reciprocal of the divisor: kh*kw when count_include_pad, else the   */
-/* number of in-range cells.                                           */
+/* reciprocal of the divisor: with count_include_pad the number of     */
+/* window cells inside the padded input (kh*kw for every floor-mode    */
+/* window; fewer for a ceil-mode window that overhangs the padding),   */
+/* else the number of in-range cells.                                  */
 /* ------------------------------------------------------------------ */
 BSO_API void bso_avgpool(const float *x, float *y, int64_t N, int64_t C, int64_t H, int64_t W,
                          int64_t kh, int64_t kw, int64_t sh, int64_t sw, int64_t ph, int64_t pw,
-                         int count_include_pad)
+                         int count_include_pad, int ceil_mode)
 {
-    const int64_t Ho = bso_pool_out(H, kh, sh, ph), Wo = bso_pool_out(W, kw, sw, pw);
+    const int64_t Ho = bso_pool_out(H, kh, sh, ph, ceil_mode), Wo = bso_pool_out(W, kw, sw, pw, ceil_mode);
 #pragma omp parallel for schedule(static)
     for (int64_t plane = 0; plane < N * C; ++plane) {
         const float *xp = x + plane * H * W;
@@ -186,7 +194,10 @@ BSO_API void bso_avgpool(const float *x, float *y, int64_t N, int64_t C, int64_t
                         ++cells;
                     }
                 }
-                const float inv = 1.0f / (float)(count_include_pad ? kh * kw : cells);
+                const int64_t h0 = oh * sh - ph, w0 = ow * sw - pw;
+                const int64_t hp = (h0 + kh < H + ph ? h0 + kh : H + ph) - h0;  /* rows inside the padded input */
+                const int64_t wp = (w0 + kw < W + pw ? w0 + kw : W + pw) - w0;
+                const float inv = 1.0f / (float)(count_include_pad ? hp * wp : cells);
                 y[(plane * Ho + oh) * Wo + ow] = sum * inv;
             }
         }

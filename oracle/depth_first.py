@@ -33,8 +33,8 @@ def _regions(layers, h_in, w_in, rows, cols):
     for l in layers:
         h, w = sizes[-1]
         if l["kind"] in ("maxpool", "avgpool"):
-            h = (h + 2 * l["p"][0] - l["k"][0]) // l["s"][0] + 1
-            w = (w + 2 * l["p"][1] - l["k"][1]) // l["s"][1] + 1
+            h = L.pool_out(h, l["k"][0], l["s"][0], l["p"][0], l.get("ceil_mode", False))
+            w = L.pool_out(w, l["k"][1], l["s"][1], l["p"][1], l.get("ceil_mode", False))
         sizes.append((h, w))
     need = [None] * (len(layers) + 1)
     need[len(layers)] = (rows, cols)
@@ -81,7 +81,10 @@ def _pool_region(kind, layer, src, src_rows, src_cols, plane_hw, out_rows, out_c
                 acc = np.zeros((n, c), np.float32)
                 for v in vals:
                     acc = (acc + v).astype(np.float32)
-                div = kh * kw if layer.get("count_include_pad", True) else len(cells)
+                # count_include_pad: the window cells inside the padded plane (kh*kw in floor mode)
+                hp = min(oh * sh - ph + kh, h + ph) - (oh * sh - ph)
+                wp = min(ow * sw - pw + kw, w + pw) - (ow * sw - pw)
+                div = hp * wp if layer.get("count_include_pad", True) else len(cells)
                 inv = np.float32(1.0) / np.float32(div)
                 out[:, :, oh - oh0, ow - ow0] = (acc * inv).astype(np.float32)
     return out, idx

@@ -33,10 +33,10 @@ def lib():
                                                  _f32p, _f32p, _f32p, _f32p, C.c_double]
         L.bso_relu.argtypes = [_f32p, _f32p, _i64]
         L.bso_add.argtypes = [_f32p, _f32p, _f32p, _i64]
-        L.bso_pool_out.argtypes = [_i64] * 4
+        L.bso_pool_out.argtypes = [_i64] * 4 + [C.c_int]
         L.bso_pool_out.restype = _i64
-        L.bso_maxpool.argtypes = [_f32p, _f32p, _i32p] + [_i64] * 10
-        L.bso_avgpool.argtypes = [_f32p, _f32p] + [_i64] * 10 + [C.c_int]
+        L.bso_maxpool.argtypes = [_f32p, _f32p, _i32p] + [_i64] * 10 + [C.c_int]
+        L.bso_avgpool.argtypes = [_f32p, _f32p] + [_i64] * 10 + [C.c_int, C.c_int]
         for f in (L.bso_round_bf16, L.bso_bn_fold, L.bso_batchnorm, L.bso_batchnorm_textbook_f64,
                   L.bso_relu, L.bso_add, L.bso_maxpool, L.bso_avgpool):
             f.restype = None
@@ -111,32 +111,32 @@ def add(a, r) -> np.ndarray:
     return y
 
 
-def pool_out(size, k, s, p) -> int:
-    return int(lib().bso_pool_out(int(size), int(k), int(s), int(p)))
+def pool_out(size, k, s, p, ceil_mode=False) -> int:
+    return int(lib().bso_pool_out(int(size), int(k), int(s), int(p), 1 if ceil_mode else 0))
 
 
-def maxpool(x, k, s, p, return_indices=False):
+def maxpool(x, k, s, p, return_indices=False, ceil_mode=False):
     x = _f32(x)
     n, c, h, w = _nchw(x)
-    ho, wo = pool_out(h, k[0], s[0], p[0]), pool_out(w, k[1], s[1], p[1])
+    ho, wo = pool_out(h, k[0], s[0], p[0], ceil_mode), pool_out(w, k[1], s[1], p[1], ceil_mode)
     if ho < 1 or wo < 1:
         raise ValueError("pool output would be empty")
     y = np.empty((n, c, ho, wo), np.float32)
     idx = np.empty((n, c, ho, wo), np.int32)
     lib().bso_maxpool(_p(x), _p(y), idx.ctypes.data_as(_i32p), n, c, h, w,
-                      k[0], k[1], s[0], s[1], p[0], p[1])
+                      k[0], k[1], s[0], s[1], p[0], p[1], 1 if ceil_mode else 0)
     return (y, idx) if return_indices else y
 
 
-def avgpool(x, k, s, p, count_include_pad=True) -> np.ndarray:
+def avgpool(x, k, s, p, count_include_pad=True, ceil_mode=False) -> np.ndarray:
     x = _f32(x)
     n, c, h, w = _nchw(x)
-    ho, wo = pool_out(h, k[0], s[0], p[0]), pool_out(w, k[1], s[1], p[1])
+    ho, wo = pool_out(h, k[0], s[0], p[0], ceil_mode), pool_out(w, k[1], s[1], p[1], ceil_mode)
     if ho < 1 or wo < 1:
         raise ValueError("pool output would be empty")
     y = np.empty((n, c, ho, wo), np.float32)
     lib().bso_avgpool(_p(x), _p(y), n, c, h, w, k[0], k[1], s[0], s[1], p[0], p[1],
-                      1 if count_include_pad else 0)
+                      1 if count_include_pad else 0, 1 if ceil_mode else 0)
     return y
 
 

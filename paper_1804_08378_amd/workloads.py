@@ -71,29 +71,32 @@ def _pair(v):
     return (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
 
 
-def maxpool(k, s=None, p=0, return_indices: bool = False) -> dict:
+def maxpool(k, s=None, p=0, return_indices: bool = False, ceil_mode: bool = False) -> dict:
     s = k if s is None else s
     return {"kind": "maxpool", "k": _pair(k), "s": _pair(s), "p": _pair(p),
-            "return_indices": bool(return_indices)}
+            "return_indices": bool(return_indices), "ceil_mode": bool(ceil_mode)}
 
 
-def avgpool(k, s=None, p=0, count_include_pad: bool = True) -> dict:
+def avgpool(k, s=None, p=0, count_include_pad: bool = True, ceil_mode: bool = False) -> dict:
     s = k if s is None else s
     return {"kind": "avgpool", "k": _pair(k), "s": _pair(s), "p": _pair(p),
-            "count_include_pad": bool(count_include_pad)}
+            "count_include_pad": bool(count_include_pad), "ceil_mode": bool(ceil_mode)}
 
 
-def pool_out(h: int, k: int, s: int, p: int) -> int:
-    """Spatial output size of a floor-mode pool (shape bookkeeping only)."""
-    return (h + 2 * p - k) // s + 1
+def pool_out(h: int, k: int, s: int, p: int, ceil_mode: bool = False) -> int:
+    """Spatial output size of a pool (shape bookkeeping only)."""
+    if not ceil_mode:
+        return (h + 2 * p - k) // s + 1
+    o = -((h + 2 * p - k) // -s) + 1
+    return o - 1 if (o - 1) * s >= h + p else o
 
 
 def output_shape(layers, shape):
     n, c, h, w = (int(v) for v in shape)
     for l in layers:
         if l["kind"] in ("maxpool", "avgpool"):
-            h = pool_out(h, l["k"][0], l["s"][0], l["p"][0])
-            w = pool_out(w, l["k"][1], l["s"][1], l["p"][1])
+            h = pool_out(h, l["k"][0], l["s"][0], l["p"][0], l.get("ceil_mode", False))
+            w = pool_out(w, l["k"][1], l["s"][1], l["p"][1], l.get("ceil_mode", False))
     return (n, c, h, w)
 
 

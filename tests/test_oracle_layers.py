@@ -266,6 +266,59 @@ def test_avgpool_sum_order_is_row_major_sequential():
 
 
 # ------------------------------------------------------------ bf16 rounding
+# ------------------------------------------------------------------ ceil mode
+def test_ceil_mode_output_size_rule():
+    """One more window when the floor-mode windows leave cells uncovered, dropped again if it
+    would start beyond the input and its leading padding; checked against the framework's own
+    shape rule for a sweep of sizes, and on hand-computed cases."""
+    assert L.pool_out(5, 2, 2, 0, True) == 3 and L.pool_out(5, 2, 2, 0, False) == 2
+    assert L.pool_out(6, 2, 2, 0, True) == 3                      # nothing uncovered: same as floor
+    assert L.pool_out(3, 2, 2, 1, True) == 2                      # third window would start at 3 >= 3 + 1 - ... dropped
+    assert L.pool_out(111, 3, 2, 0, True) == 55 and L.pool_out(112, 3, 2, 0, True) == 56
+    for size in range(1, 24):
+        for k in (1, 2, 3, 5):
+            for s in (1, 2, 3):
+                for p in range(0, k // 2 + 1):
+                    if size + 2 * p < k:
+                        continue
+                    want = F.max_pool2d(torch.zeros(1, 1, size, size), k, s, p, ceil_mode=True).shape[-1]
+                    assert L.pool_out(size, k, s, p, True) == want == wl.pool_out(size, k, s, p, True), (size, k, s, p)
+
+
+@pytest.mark.parametrize("H,W,k,s,p", [(5, 5, 2, 2, 0), (7, 9, 3, 2, 0), (7, 9, 3, 2, 1), (10, 11, 3, 3, 1),
+                                       (13, 13, (3, 2), (2, 3), (1, 0)), (6, 6, 2, 2, 0)])
+def test_ceil_mode_pools_vs_torch(H, W, k, s, p):
+    x = wl.activation((2, 3, H, W), 11)
+    t = torch.from_numpy(x)
+    y, idx = L.maxpool(x, wl._pair(k), wl._pair(s), wl._pair(p), True, True)
+    ty, tidx = F.max_pool2d(t, k, s, p, ceil_mode=True, return_indices=True)
+    assert y.shape == tuple(ty.shape)
+    assert np.array_equal(y, ty.numpy()) and np.array_equal(idx, tidx.numpy().astype(np.int32))
+    for cip in (True, False):
+        a = L.avgpool(x, wl._pair(k), wl._pair(s), wl._pair(p), cip, True)
+        ta = F.avg_pool2d(t.double(), k, s, p, ceil_mode=True, count_include_pad=cip).numpy()
+        assert a.shape == ta.shape
+        assert np.abs(a - ta).max() <= 1e-6 * max(1.0, np.abs(ta).max())
+
+
+def test_ceil_mode_average_divisor_closed_form():
+    """Constant input 1: an overhanging window averages (in-range cells) / (cells inside the
+    padded input) with count_include_pad, and exactly 1 without."""
+    x = np.ones((1, 1, 5, 5), np.float32)
+    a = L.avgpool(x, (2, 2), (2, 2), (0, 0), True, True)      # 3x3 outputs; last row/col overhang by one
+    assert a.shape == (1, 1, 3, 3)
+    assert np.array_equal(a[0, 0], np.ones((3, 3), np.float32))   # overhang is outside the padded input: not counted
+    b = L.avgpool(x, (3, 3), (2, 2), (1, 1), True, True)      # 5 + 2 - 3 = 4 -> 3 outputs, no overhang beyond padding
+    assert b.shape == (1, 1, 3, 3)
+    assert b[0, 0, 0, 0] == np.float32(4) * (np.float32(1) / np.float32(9))   # corner: 4 in-range of 9
+    c = L.avgpool(x, (3, 3), (2, 2), (1, 1), False, True)
+    assert np.array_equal(c[0, 0], np.ones((3, 3), np.float32))
+    x6 = np.ones((1, 1, 6, 6), np.float32)
+    d = L.avgpool(x6, (3, 3), (2, 2), (1, 1), True, True)     # 4 outputs; last window rows 5..7: 1 in range, 2 inside padded
+    assert d.shape == (1, 1, 4, 4)
+    assert d[0, 0, 3, 1] == np.float32(3) * (np.float32(1) / np.float32(6))   # 1 row x 3 cols in range / 2 x 3 counted
+
+
 def test_round_bf16_vs_library_and_ties():
     x = _x((1, 1, 64, 64), 13) * 100
     ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()

@@ -120,6 +120,29 @@ def _torch_pipeline(layers, x, residuals, double=False):
     return t.numpy(), idx
 
 
+def test_ceil_mode_stack_depth_first_equals_breadth_first_and_torch():
+    """A stack with ceil-mode pools (overhanging last windows): tiled depth-first execution
+    gives the breadth-first result bit for bit, which agrees with the framework's layers."""
+    import torch
+    import torch.nn.functional as F
+    layers = [wl.bn_params(3, 5), wl.relu(), wl.maxpool(3, 2, 0, True, ceil_mode=True),
+              wl.avgpool(3, 2, 1, True, ceil_mode=True), wl.relu(), wl.avgpool(2, 2, 0, False, ceil_mode=True)]
+    x = wl.activation((2, 3, 18, 21), 9)
+    ref, ref_idx, _ = bf.run_stack(layers, x)
+    assert ref.shape == wl.output_shape(layers, x.shape)
+    for tile in ((1, 1), (2, 3), (100, 100)):
+        out, idx = df.run_stack_tiled(layers, x, (), "f32", tile)
+        assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
+        assert np.array_equal(idx[0], ref_idx[0])
+    b = layers[0]
+    t = F.batch_norm(torch.from_numpy(x).double(), torch.from_numpy(b["mean"]).double(), torch.from_numpy(b["var"]).double(),
+                     torch.from_numpy(b["gamma"]).double(), torch.from_numpy(b["beta"]).double(), False, 0.0, b["eps"])
+    t = F.max_pool2d(F.relu(t), 3, 2, 0, ceil_mode=True)
+    t = F.relu(F.avg_pool2d(t, 3, 2, 1, ceil_mode=True, count_include_pad=True))
+    t = F.avg_pool2d(t, 2, 2, 0, ceil_mode=True, count_include_pad=False).numpy()
+    assert t.shape == ref.shape and np.abs(ref - t).max() <= 1e-5 * np.abs(t).max()
+
+
 @pytest.mark.parametrize("name", wl.CONFIG_NAMES)
 def test_named_configs_vs_library_pipeline_f64(name):
     """Every BASELINE configuration (batch cut to 2, planes cut to keep it quick) against
