@@ -49,7 +49,7 @@ typedef enum bs_status {
     BS_ERR_NULL = 1,        /* a required pointer is NULL                                  */
     BS_ERR_SHAPE = 2,       /* non-positive dimension, or a pooling output dimension < 1   */
     BS_ERR_PARAM = 3,       /* k < 1, s < 1, p > k/2, var + eps <= 0, non-finite parameter */
-    BS_ERR_UNSUPPORTED = 4, /* ceil_mode, dilation != 1, unknown kind/dtype, too many layers */
+    BS_ERR_UNSUPPORTED = 4, /* dilation != 1, unknown kind/dtype, too many layers          */
     BS_ERR_NOT_PLANNED = 5, /* run / info before a successful device plan                  */
     BS_ERR_NO_FIT = 6,      /* a step does not fit the on-chip budget at the smallest tile */
     BS_ERR_ALIGN = 7,       /* a device pointer is not 16-byte aligned                     */
@@ -80,14 +80,18 @@ typedef enum bs_layer_kind {
  *   and shift = beta - mean * scale, each rounded once to float32, and evaluates
  *   y = fma(x, scale, shift) in float32.
  * BS_MAXPOOL / BS_AVGPOOL: window kh x kw, stride sh x sw, zero/ignored padding
- *   ph x pw on each side (p <= k/2), floor output size H_out = (H + 2p - k) / s + 1.
+ *   ph x pw on each side (p <= k/2), output size H_out = (H + 2p - k) / s + 1 rounded
+ *   down, or with ceil_mode != 0 rounded up unless the extra window would start at or
+ *   beyond H + p (a last window may then overhang the padded input; its cells outside
+ *   the input count like padding).
  *   Padding cells are never a maximum candidate and add nothing to an average.
  *   Max: first maximum in row-major window order wins; with return_indices the
  *   layer also yields int32 ih * W + iw of the winner in its own input plane.
  *   Avg: float32 sum over the in-range cells in row-major order, multiplied by the
- *   float32 reciprocal of kh * kw (count_include_pad != 0) or of the number of
- *   in-range cells (count_include_pad == 0).
- *   ceil_mode != 0 or a dilation other than 0 / 1 is rejected (BS_ERR_UNSUPPORTED).
+ *   float32 reciprocal of the number of window cells inside the padded input
+ *   (count_include_pad != 0: kh * kw, fewer only for an overhanging ceil-mode window)
+ *   or of the number of in-range cells (count_include_pad == 0).
+ *   A dilation other than 0 / 1 is rejected (BS_ERR_UNSUPPORTED).
  */
 typedef struct bs_layer_desc {
     int32_t kind; /* bs_layer_kind */

@@ -15,7 +15,8 @@ struct Op {
     int32_t kind = 0;
     int32_t layer = -1;       // index in the layer list
     int32_t kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0;
-    int32_t count_include_pad = 1;
+    int32_t count_include_pad = 1;  // average: 0 in-range cells, 1 kh * kw, 2 cells inside the padded plane
+    int32_t ceil = 0;         // ceil mode added a last window that overhangs the padded plane
     int32_t idx_slot = -1;    // stack-wide index-output number (max pool with return_indices)
     int32_t res_slot = -1;    // stack-wide residual number (Add)
     int32_t param_off = -1;   // BN: float offset of scale[C] in the parameter table; shift follows

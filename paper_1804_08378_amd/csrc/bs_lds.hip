@@ -34,7 +34,7 @@ template <class P>
 static bool pool_is(const PoolK &q)
 {
     return q.kind == P::kind() && q.kh == P::kh() && q.kw == P::kw() && q.sh == P::sh() && q.sw == P::sw() &&
-           q.ph == P::ph() && q.pw == P::pw() && (q.kind == OP_MAXPOOL || (q.count_include_pad != 0) == (P::cip() != 0));
+           q.ph == P::ph() && q.pw == P::pw() && (q.kind == OP_MAXPOOL || q.count_include_pad == P::cip());
 }
 
 enum { LAUNCH = 0, DRY_SIGNATURE = 1, DRY_FULL = 2 };  // what the table walk does on a match
@@ -124,7 +124,7 @@ std::string lds_expr(const LdsSeqK &k, bool bf16, bool want_idx)
     for (int l = 1; l <= k.n_levels; ++l) {
         const PoolK &p = k.pool[l];
         std::snprintf(b, sizeof b, ", bs::Lvl<bs::PoolSpec<%d, %d, %d, %d, %d, %d, %d, %d>, %d>", p.kind, p.kh, p.kw, p.sh,
-                      p.sw, p.ph, p.pw, (p.kind == OP_MAXPOOL || p.count_include_pad) ? 1 : 0, ew_code(k.level[l]));
+                      p.sw, p.ph, p.pw, p.kind == OP_MAXPOOL ? 1 : p.count_include_pad, ew_code(k.level[l]));
         e += b;
     }
     return e + ">";

@@ -255,15 +255,17 @@ BS_DEV void pool_strip(const P &p, const float *src, int32_t d_rt, int32_t vo, i
     if (is_max) {
 #pragma unroll
         for (int e = 0; e < VO; ++e) val[e] = acc[e];
-    } else if (p.cip()) {
+    } else if (p.cip() == 1) {
 #pragma unroll
         for (int e = 0; e < VO; ++e) val[e] = acc[e] * p.inv_kk();
     } else {
-        const int32_t nr = min(h0 + p.kh(), Hp) - max(h0, 0);
+        // 0: in-range cells; 2 (ceil mode with count_include_pad): cells inside the padded plane
+        const bool padded = p.cip() == 2;
+        const int32_t nr = padded ? min(h0 + p.kh(), Hp + p.ph()) - h0 : min(h0 + p.kh(), Hp) - max(h0, 0);
 #pragma unroll
         for (int e = 0; e < VO; ++e) {
             const int32_t we = w0 + e * p.sw();
-            const int32_t nc = min(we + p.kw(), Wp) - max(we, 0);
+            const int32_t nc = padded ? min(we + p.kw(), Wp + p.pw()) - we : min(we + p.kw(), Wp) - max(we, 0);
             // windows wholly outside the plane can make nr * nc <= 0; such outputs are never stored
             val[e] = acc[e] * (1.0f / (float)max(nr * nc, 1));
         }
@@ -337,12 +339,14 @@ BS_DEV void pool_block(const P &p, const float *src, int32_t pitch, int32_t nrow
                     for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
                         for (int dw = 0; dw < KW; ++dw) sum = sum + w[dh][D + e * SW + dw];
-                    if (p.cip()) {
+                    if (p.cip() == 1) {
                         val[e] = sum * p.inv_kk();
                     } else {
+                        // 0: in-range cells; 2 (ceil mode with count_include_pad): cells inside the padded plane
+                        const bool padded = p.cip() == 2;
                         const int32_t we = w0 + e * SW;
-                        const int32_t nr = min(hi + KH, Hp) - max(hi, 0);
-                        const int32_t nc = min(we + KW, Wp) - max(we, 0);
+                        const int32_t nr = padded ? min(hi + KH, Hp + P::ph()) - hi : min(hi + KH, Hp) - max(hi, 0);
+                        const int32_t nc = padded ? min(we + KW, Wp + P::pw()) - we : min(we + KW, Wp) - max(we, 0);
                         // windows wholly outside the plane can make nr * nc <= 0; such outputs are never stored
                         val[e] = sum * (1.0f / (float)max(nr * nc, 1));
                     }

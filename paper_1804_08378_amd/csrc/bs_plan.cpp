@@ -51,13 +51,16 @@ bs_status build_operations(bs_stack *s)
         case BS_AVGPOOL: {
             const bs_layer_desc &d = L.desc;
             op.kh = d.kh; op.kw = d.kw; op.sh = d.sh; op.sw = d.sw; op.ph = d.ph; op.pw = d.pw;
+            op.ceil = d.ceil_mode ? 1 : 0;
             if (d.kind == BS_MAXPOOL) {
                 op.kind = OP_MAXPOOL;
                 if (d.return_indices) op.idx_slot = idx++;
                 s->ops.push_back(op);
             } else {
                 op.kind = OP_AVGSUM;
-                op.count_include_pad = d.count_include_pad ? 1 : 0;
+                // 0: in-range cells; 1: kh * kw; 2: the window cells inside the padded plane (ceil
+                // mode with count_include_pad: a last window may overhang the padding)
+                op.count_include_pad = d.count_include_pad ? (L.desc.ceil_mode ? 2 : 1) : 0;
                 s->ops.push_back(op);
                 Op norm;
                 norm.kind = OP_AVGNORM;
@@ -220,6 +223,7 @@ static void lds_geometry(const bs_stack *s, int32_t first_op, int32_t n_ops, int
 // max pool in the middle of a sequence: its whole output must then be computed by tiles.
 static bool covers_input(const Op &op)
 {
+    if (op.ceil) return op.kh >= op.sh && op.kw >= op.sw;  // the extra last window reaches the plane's end
     auto ok = [](int32_t size, int32_t k, int32_t st, int32_t p) {
         return k >= st && ((size + 2 * p - k) % st) <= p;
     };
@@ -285,6 +289,7 @@ static bool direct_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops
         const Op &op = s->ops[i];
         if (op_is_elementwise(op.kind)) continue;
         if (op.kh != op.sh || op.kw != op.sw || op.ph != 0 || op.pw != 0) return false;
+        if (op.ceil) return false;  // its last windows overhang the plane: the kernel reads whole windows
         if (op.in_w % vec != 0 || vec % op.kw != 0) return false;
         if (op.kh > 4 || (op.kw != 1 && op.kw != 2 && op.kw != 4 && op.kw != 8)) return false;
     }

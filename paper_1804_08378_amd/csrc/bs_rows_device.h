@@ -258,6 +258,10 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
                         const int32_t nr_ = min(hw + KH, k.H) - max(hw, 0);
                         const int32_t nc_ = min(w0 + KW, k.W) - max(w0, 0);
                         inv = 1.0f / (float)max(nr_ * nc_, 1);
+                    } else if (k.pool.count_include_pad == 2) {  // ceil mode: cells inside the padded plane
+                        const int32_t nr_ = min(hw + KH, k.H + PH) - hw;
+                        const int32_t nc_ = min(w0 + KW, k.W + PW) - w0;
+                        inv = 1.0f / (float)max(nr_ * nc_, 1);
                     }
                     y[e] = round_store<BF16>(sum * inv);
                     yi[e] = 0;
@@ -429,10 +433,11 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
 #pragma unroll
                     for (int dw = 0; dw < KW1; ++dw) sum = sum + w0[dh][n * SW1 + dw];
                 float inv = k.pool1.inv_kk;
-                if (!k.pool1.count_include_pad) {
+                if (k.pool1.count_include_pad != 1) {
                     const int32_t w0c = (c1s + n) * SW1 - PW1;
-                    const int32_t nr_ = min(hw + KH1, k.H) - max(hw, 0);
-                    const int32_t nc_ = min(w0c + KW1, k.W) - max(w0c, 0);
+                    const bool padded = k.pool1.count_include_pad == 2;  // ceil mode: cells inside the padded plane
+                    const int32_t nr_ = padded ? min(hw + KH1, k.H + PH1) - hw : min(hw + KH1, k.H) - max(hw, 0);
+                    const int32_t nc_ = padded ? min(w0c + KW1, k.W + PW1) - w0c : min(w0c + KW1, k.W) - max(w0c, 0);
                     inv = 1.0f / (float)max(nr_ * nc_, 1);
                 }
                 y[n] = round_store<BF16>(sum * inv);
@@ -509,9 +514,10 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
 #pragma unroll
                     for (int dw = 0; dw < KW2; ++dw) sum = sum + win1[dh][e * SW2 + dw];
                 float inv = k.pool2.inv_kk;
-                if (!k.pool2.count_include_pad) {
-                    const int32_t nr_ = min(r1w + KH2, k.H1) - max(r1w, 0);
-                    const int32_t nc_ = min(w0 + KW2, k.W1) - max(w0, 0);
+                if (k.pool2.count_include_pad != 1) {
+                    const bool padded = k.pool2.count_include_pad == 2;  // ceil mode: cells inside the padded plane
+                    const int32_t nr_ = padded ? min(r1w + KH2, k.H1 + PH2) - r1w : min(r1w + KH2, k.H1) - max(r1w, 0);
+                    const int32_t nc_ = padded ? min(w0 + KW2, k.W1 + PW2) - w0 : min(w0 + KW2, k.W1) - max(w0, 0);
                     inv = 1.0f / (float)max(nr_ * nc_, 1);
                 }
                 y[e] = round_store<BF16>(sum * inv);

@@ -106,7 +106,6 @@ bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers, const i
                 break;
             case BS_MAXPOOL:
             case BS_AVGPOOL: {
-                if (d.ceil_mode != 0) { err = BS_ERR_UNSUPPORTED; break; }
                 if ((d.dilation_h != 0 && d.dilation_h != 1) || (d.dilation_w != 0 && d.dilation_w != 1)) {
                     err = BS_ERR_UNSUPPORTED;
                     break;
@@ -116,8 +115,18 @@ bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers, const i
                     d.sw > 1024) { err = BS_ERR_PARAM; break; }
                 const int64_t nh = cur[2] + 2 * d.ph - d.kh, nw = cur[3] + 2 * d.pw - d.kw;
                 if (nh < 0 || nw < 0) { err = BS_ERR_SHAPE; break; }
-                cur[2] = nh / d.sh + 1;
-                cur[3] = nw / d.sw + 1;
+                // floor mode: the windows that fit; ceil mode: one more window if cells are left
+                // uncovered, unless it would start beyond the input and its leading padding
+                auto out_size = [&](int64_t in, int64_t n, int64_t st, int64_t pad) {
+                    int64_t o = n / st + 1;
+                    if (d.ceil_mode != 0 && n % st != 0 && o * st < in + pad) ++o;
+                    return o;
+                };
+                const int64_t oh = out_size(cur[2], nh, d.sh, d.ph), ow = out_size(cur[3], nw, d.sw, d.pw);
+                // recorded only where it changes the result: an overhanging last window
+                L.desc.ceil_mode = (oh != nh / d.sh + 1 || ow != nw / d.sw + 1) ? 1 : 0;
+                cur[2] = oh;
+                cur[3] = ow;
                 s->has_pool = true;
                 if (d.kind == BS_MAXPOOL && d.return_indices) {
                     if (s->n_idx >= BS_MAX_INDEX_OUTPUTS) { err = BS_ERR_UNSUPPORTED; break; }

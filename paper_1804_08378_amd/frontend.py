@@ -50,17 +50,18 @@ def layer_desc(m: nn.Module) -> Optional[dict]:
     if isinstance(m, nn.ReLU):
         return {"kind": "relu"}
     if isinstance(m, nn.MaxPool2d):
-        if m.ceil_mode or _pair(m.dilation) != (1, 1) or m.return_indices:
+        if _pair(m.dilation) != (1, 1) or m.return_indices:
             return None  # a Sequential cannot pass on the (values, indices) pair anyway
         k = _pair(m.kernel_size)
         return {"kind": "maxpool", "k": k, "s": _pair(m.stride if m.stride is not None else k),
-                "p": _pair(m.padding), "return_indices": False}
+                "p": _pair(m.padding), "return_indices": False, "ceil_mode": bool(m.ceil_mode)}
     if isinstance(m, nn.AvgPool2d):
-        if m.ceil_mode or m.divisor_override is not None:
+        if m.divisor_override is not None:
             return None
         k = _pair(m.kernel_size)
         return {"kind": "avgpool", "k": k, "s": _pair(m.stride if m.stride is not None else k),
-                "p": _pair(m.padding), "count_include_pad": bool(m.count_include_pad)}
+                "p": _pair(m.padding), "count_include_pad": bool(m.count_include_pad),
+                "ceil_mode": bool(m.ceil_mode)}
     if isinstance(m, (nn.Identity, nn.Dropout, nn.Dropout2d)):
         return {}  # identity at inference time
     return None

@@ -43,8 +43,9 @@ def test_create_rejects_bad_arguments():
     assert _status(bs.bs_stack_create, [wl.maxpool(2, 2, 2)], (1, 4, 8, 8), "f32") == 3  # p > k/2
     assert _status(bs.bs_stack_create, [wl.maxpool(0, 1, 0)], (1, 4, 8, 8), "f32") == 3
     assert _status(bs.bs_stack_create, [wl.avgpool(2, 0, 0)], (1, 4, 8, 8), "f32") == 3
-    ceil = dict(wl.maxpool(2, 2), ceil_mode=True)
-    assert _status(bs.bs_stack_create, [ceil], (1, 4, 8, 8), "f32") == 4
+    h = bs.bs_stack_create([wl.maxpool(2, 2, ceil_mode=True)], (1, 4, 9, 9), "f32")  # ceil mode: 5 x 5 outputs
+    assert bs.bs_stack_output_shape(h) == (1, 4, 5, 5)
+    bs.bs_stack_destroy(h)
     dil = dict(wl.maxpool(2, 2), dilation=(2, 2))
     assert _status(bs.bs_stack_create, [dil], (1, 4, 8, 8), "f32") == 4
     bad = dict(ok_bn, var=np.array([1, 1, -1, 1], np.float32))

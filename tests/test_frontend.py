@@ -52,9 +52,10 @@ def test_aggregation_detection_finds_maximal_runs():
     m = vgg_like()
     assert fe.find_runs(m) == [(1, 4), (5, 10), (11, 12)]
     # layers the library does not take end a run
-    seq = nn.Sequential(nn.ReLU(), nn.MaxPool2d(2, ceil_mode=True), nn.ReLU(), nn.BatchNorm2d(4, track_running_stats=False),
+    seq = nn.Sequential(nn.ReLU(), nn.MaxPool2d(2, return_indices=True), nn.ReLU(), nn.MaxPool2d(2, ceil_mode=True),
+                        nn.BatchNorm2d(4, track_running_stats=False),
                         nn.MaxPool2d(2, dilation=2), nn.AvgPool2d(2, divisor_override=3), nn.Dropout(), nn.Identity())
-    assert fe.find_runs(seq) == [(0, 1), (2, 3)]  # the trailing Dropout/Identity run holds no real layer
+    assert fe.find_runs(seq) == [(0, 1), (2, 4)]  # the trailing Dropout/Identity run holds no real layer
 
 
 def test_optimize_replaces_first_layer_and_blanks_the_rest():

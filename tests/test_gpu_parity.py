@@ -338,6 +338,34 @@ def test_run_time_builds(shape, dtype):
         check(layers, x, res, dtype, f"built/{name}{shape}/off", jit=-1)
 
 
+# ------------------------------------------------------------------ ceil mode
+def _ceil_stacks(c):
+    return {
+        "squeeze": [wl.relu(), wl.maxpool(3, 2, 0, True, ceil_mode=True)],
+        "googlenet": [wl.maxpool(3, 2, 0, False, ceil_mode=True), wl.bn_params(c, 90), wl.relu()],
+        "max2s2": [wl.bn_params(c, 91), wl.relu(), wl.maxpool(2, 2, 0, True, ceil_mode=True)],
+        "avg_padded_count": [wl.avgpool(3, 2, 1, True, ceil_mode=True), wl.relu()],
+        "avg_in_range_count": [wl.avgpool(3, 2, 1, False, ceil_mode=True)],
+        "avg2s2": [wl.relu(), wl.avgpool(2, 2, 0, True, ceil_mode=True)],
+        "two_pools": [wl.bn_params(c, 92), wl.relu(), wl.maxpool(3, 2, 0, True, ceil_mode=True),
+                      wl.avgpool(3, 2, 1, True, ceil_mode=True), wl.relu()],
+        "three_pools": [wl.maxpool(3, 2, 1, False, ceil_mode=True), wl.relu(), wl.avgpool(2, 2, 0, False, ceil_mode=True),
+                        wl.maxpool(3, 1, 1, True, ceil_mode=True)],
+    }
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 18, 24), (1, 2, 21, 21), (2, 2, 13, 16), (1, 4, 8, 8)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ceil_mode_pools(shape, dtype):
+    """Ceil-mode pools: one more, overhanging, window per dimension where the floor-mode windows
+    leave cells uncovered; its cells outside the plane count like padding."""
+    for name, layers in _ceil_stacks(shape[1]).items():
+        x = wl.activation(shape, 74, dtype)
+        check(layers, x, [], dtype, f"ceil/{name}{shape}")
+        check(layers, x, [], dtype, f"ceil/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
+        check(layers, x, [], dtype, f"ceil/{name}{shape}/layer-by-layer", breadth_first=1)
+
+
 # ------------------------------------------------------------------ special values
 def test_signed_zero_and_subnormals_follow_the_oracle():
     """ReLU maps -0 to +0, subnormal values pass through unchanged, and max pooling of windows
