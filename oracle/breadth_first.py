@@ -38,6 +38,10 @@ def run_stack(layers, x, residuals=(), dtype: str = "f32", keep_intermediates: b
                               layer["eps"])
         elif kind == "relu":
             cur = L.relu(cur)
+        elif kind == "leaky_relu":
+            cur = L.leaky_relu(cur, layer["slope"])
+        elif kind == "clamp":
+            cur = L.clamp(cur, layer["lo"], layer["hi"])
         elif kind == "add":
             if not res:
                 raise ValueError("stack has more Add layers than residual tensors")

@@ -107,6 +107,26 @@ BSO_API void bso_relu(const float *x, float *y, int64_t n)
     for (int64_t i = 0; i < n; ++i) y[i] = (x[i] > 0.0f) ? x[i] : 0.0f;
 }
 
+/* Leaky ReLU (one of the further element-wise activations Section 2 alludes to with
+ * "BatchNorm, ReLU, ..."): positive values pass, everything else is multiplied by the
+ * slope (one float32 rounding). */
+BSO_API void bso_leaky_relu(const float *x, float *y, int64_t n, float slope)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) y[i] = (x[i] > 0.0f) ? x[i] : x[i] * slope;
+}
+
+/* Clamp to [lo, hi] (ReLU6 = clamp to [0, 6]; "hard tanh"): first raised to lo -- anything
+ * not above lo, NaN included, becomes lo -- then lowered to hi. */
+BSO_API void bso_clamp(const float *x, float *y, int64_t n, float lo, float hi)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const float t = (x[i] > lo) ? x[i] : lo;
+        y[i] = (t < hi) ? t : hi;
+    }
+}
+
 /* Residual add: y = a + r, one float32 rounding. */
 BSO_API void bso_add(const float *a, const float *r, float *y, int64_t n)
 {

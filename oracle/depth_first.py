@@ -118,6 +118,10 @@ def run_stack_tiled(layers, x, residuals=(), dtype="f32", tile=(1, 1)):
                     cur = L.batchnorm(cur, l["gamma"], l["beta"], l["mean"], l["var"], l["eps"])
                 elif kind == "relu":
                     cur = L.relu(cur)
+                elif kind == "leaky_relu":
+                    cur = L.leaky_relu(cur, l["slope"])
+                elif kind == "clamp":
+                    cur = L.clamp(cur, l["lo"], l["hi"])
                 elif kind == "add":
                     r = np.ascontiguousarray(residuals[res_i], np.float32)
                     res_i += 1

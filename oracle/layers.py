@@ -33,12 +33,14 @@ def lib():
                                                  _f32p, _f32p, _f32p, _f32p, C.c_double]
         L.bso_relu.argtypes = [_f32p, _f32p, _i64]
         L.bso_add.argtypes = [_f32p, _f32p, _f32p, _i64]
+        L.bso_leaky_relu.argtypes = [_f32p, _f32p, _i64, C.c_float]
+        L.bso_clamp.argtypes = [_f32p, _f32p, _i64, C.c_float, C.c_float]
         L.bso_pool_out.argtypes = [_i64] * 4 + [C.c_int]
         L.bso_pool_out.restype = _i64
         L.bso_maxpool.argtypes = [_f32p, _f32p, _i32p] + [_i64] * 10 + [C.c_int]
         L.bso_avgpool.argtypes = [_f32p, _f32p] + [_i64] * 10 + [C.c_int, C.c_int]
         for f in (L.bso_round_bf16, L.bso_bn_fold, L.bso_batchnorm, L.bso_batchnorm_textbook_f64,
-                  L.bso_relu, L.bso_add, L.bso_maxpool, L.bso_avgpool):
+                  L.bso_relu, L.bso_add, L.bso_maxpool, L.bso_avgpool, L.bso_leaky_relu, L.bso_clamp):
             f.restype = None
         _lib = L
     return _lib
@@ -99,6 +101,20 @@ def relu(x) -> np.ndarray:
     x = _f32(x)
     y = np.empty_like(x)
     lib().bso_relu(_p(x), _p(y), x.size)
+    return y
+
+
+def leaky_relu(x, slope) -> np.ndarray:
+    x = _f32(x)
+    y = np.empty_like(x)
+    lib().bso_leaky_relu(_p(x), _p(y), x.size, float(np.float32(slope)))
+    return y
+
+
+def clamp(x, lo, hi) -> np.ndarray:
+    x = _f32(x)
+    y = np.empty_like(x)
+    lib().bso_clamp(_p(x), _p(y), x.size, float(np.float32(lo)), float(np.float32(hi)))
     return y
 
 

@@ -63,6 +63,18 @@ def relu() -> dict:
     return {"kind": "relu"}
 
 
+def leaky_relu(slope: float = 0.01) -> dict:
+    return {"kind": "leaky_relu", "slope": float(slope)}
+
+
+def clamp(lo: float, hi: float) -> dict:
+    return {"kind": "clamp", "lo": float(lo), "hi": float(hi)}
+
+
+def relu6() -> dict:
+    return clamp(0.0, 6.0)
+
+
 def add() -> dict:
     return {"kind": "add"}
 

@@ -266,6 +266,37 @@ def test_avgpool_sum_order_is_row_major_sequential():
 
 
 # ------------------------------------------------------------ bf16 rounding
+# ------------------------------------------------------------------ further activations
+def test_leaky_relu_closed_forms_and_library():
+    x = np.array([-4.0, -1.0, -0.0, 0.0, 0.5, 3.0, -1e-30, np.inf, -np.inf], np.float32).reshape(1, 1, 3, 3)
+    y = L.leaky_relu(x, 0.25)
+    assert np.array_equal(y.ravel(), np.array([-1.0, -0.25, -0.0, 0.0, 0.5, 3.0, -2.5e-31, np.inf, -np.inf], np.float32))
+    assert np.signbit(y.ravel()[2]) and not np.signbit(y.ravel()[3])       # -0 * slope = -0; +0 * slope = +0
+    assert np.array_equal(L.leaky_relu(x, 1.0), x)                          # slope 1: identity
+    fin = x[np.isfinite(x)]
+    assert np.array_equal(L.leaky_relu(fin, 0.0), L.relu(fin))             # slope 0: ReLU up to the sign of zero
+    r = wl.activation((2, 3, 9, 11), 21)
+    for slope in (0.01, 0.2, 1.5):
+        assert np.array_equal(L.leaky_relu(r, slope), F.leaky_relu(torch.from_numpy(r), slope).numpy())
+    # one float32 rounding of the product
+    assert L.leaky_relu(np.float32([-3.0]).reshape(1, 1, 1, 1), 0.1).ravel()[0] == np.float32(-3.0) * np.float32(0.1)
+
+
+def test_clamp_closed_forms_and_library():
+    x = np.array([-7.0, -1.0, -0.0, 0.0, 0.5, 6.0, 6.5, np.nan, np.inf], np.float32).reshape(1, 1, 3, 3)
+    y = L.clamp(x, 0.0, 6.0).ravel()                                        # ReLU6
+    assert np.array_equal(y, np.array([0.0, 0.0, 0.0, 0.0, 0.5, 6.0, 6.0, 0.0, 6.0], np.float32))
+    assert not np.signbit(y[2])                                             # -0 is not above +0: becomes +0
+    assert np.array_equal(L.clamp(x, -1.0, 1.0).ravel(), np.array([-1, -1, -0.0, 0, 0.5, 1, 1, -1, 1], np.float32))
+    r = wl.activation((2, 3, 9, 11), 22) * 4
+    assert np.array_equal(L.clamp(r, 0.0, 6.0), F.relu6(torch.from_numpy(r)).numpy())
+    assert np.array_equal(L.clamp(r, -0.5, 2.0), F.hardtanh(torch.from_numpy(r), -0.5, 2.0).numpy())
+    assert np.array_equal(L.clamp(r, 0.0, np.inf), L.relu(r))               # [0, inf) is ReLU
+    # idempotent, and ordered bounds hold for every element
+    c = L.clamp(r, -0.5, 2.0)
+    assert np.array_equal(L.clamp(c, -0.5, 2.0), c) and c.min() >= -0.5 and c.max() <= 2.0
+
+
 # ------------------------------------------------------------------ ceil mode
 def test_ceil_mode_output_size_rule():
     """One more window when the floor-mode windows leave cells uncovered, dropped again if it

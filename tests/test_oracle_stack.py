@@ -120,6 +120,31 @@ def _torch_pipeline(layers, x, residuals, double=False):
     return t.numpy(), idx
 
 
+def test_activation_stack_depth_first_equals_breadth_first_and_torch():
+    """Leaky ReLU and clamp inside a pooled stack, f32 and bf16: depth-first equals
+    breadth-first bit for bit; f32 agrees with the framework's layers."""
+    import torch
+    import torch.nn.functional as F
+    layers = [wl.leaky_relu(0.1), wl.maxpool(3, 2, 1, True), wl.relu6(), wl.avgpool(2, 2, 0), wl.clamp(-0.25, 0.75)]
+    x = wl.activation((2, 3, 12, 16), 10) * 5
+    for dtype in ("f32", "bf16"):
+        xin = L_round(x, dtype)
+        ref, ref_idx, _ = bf.run_stack(layers, xin, (), dtype)
+        for tile in ((1, 1), (2, 3), (100, 100)):
+            out, idx = df.run_stack_tiled(layers, xin, (), dtype, tile)
+            assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
+            assert np.array_equal(idx[0], ref_idx[0])
+    ref, _, _ = bf.run_stack(layers, x)
+    t = F.max_pool2d(F.leaky_relu(torch.from_numpy(x), 0.1), 3, 2, 1)
+    t = F.hardtanh(F.avg_pool2d(F.relu6(t), 2, 2), -0.25, 0.75).numpy()
+    assert np.abs(ref - t).max() <= 1e-6
+
+
+def L_round(x, dtype):
+    from oracle import layers as L
+    return L.round_bf16(x) if dtype == "bf16" else x
+
+
 def test_ceil_mode_stack_depth_first_equals_breadth_first_and_torch():
     """A stack with ceil-mode pools (overhanging last windows): tiled depth-first execution
     gives the breadth-first result bit for bit, which agrees with the framework's layers."""
