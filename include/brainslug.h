@@ -68,7 +68,9 @@ typedef enum bs_layer_kind {
     BS_RELU = 2,      /* y = x > 0 ? x : +0   (Section 2: f(x) = max(0, x))                    */
     BS_ADD = 3,       /* y = x + r, r = the next residual tensor passed to bs_stack_run        */
     BS_MAXPOOL = 4,   /* Section 2 pooling, maximum; optional argmax output                    */
-    BS_AVGPOOL = 5    /* Section 2 pooling, average (window sum, then normalisation; Listing 2) */
+    BS_AVGPOOL = 5,   /* Section 2 pooling, average (window sum, then normalisation; Listing 2) */
+    BS_LEAKY_RELU = 6, /* y = x > 0 ? x : x * negative_slope                                   */
+    BS_CLAMP = 7      /* y = min(max(x, clamp_min), clamp_max): ReLU6, hard tanh               */
 } bs_layer_kind;
 
 /*
@@ -79,6 +81,9 @@ typedef enum bs_layer_kind {
  *   The library folds them once, in float64, into scale = gamma / sqrt(var + eps)
  *   and shift = beta - mean * scale, each rounded once to float32, and evaluates
  *   y = fma(x, scale, shift) in float32.
+ * BS_LEAKY_RELU / BS_CLAMP: further element-wise activations (Section 2 lists the class as
+ *   "BatchNorm, ReLU, ..."); finite parameters, clamp_min <= clamp_max.  A value not above
+ *   clamp_min (NaN included) becomes clamp_min.
  * BS_MAXPOOL / BS_AVGPOOL: window kh x kw, stride sh x sw, zero/ignored padding
  *   ph x pw on each side (p <= k/2), output size H_out = (H + 2p - k) / s + 1 rounded
  *   down, or with ceil_mode != 0 rounded up unless the extra window would start at or
@@ -105,6 +110,9 @@ typedef struct bs_layer_desc {
     const float *beta;         /* host */
     const float *running_mean; /* host */
     const float *running_var;  /* host */
+    float negative_slope;      /* BS_LEAKY_RELU */
+    float clamp_min, clamp_max; /* BS_CLAMP */
+    float reserved;
 } bs_layer_desc;
 
 typedef struct bs_stack bs_stack; /* opaque */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "libbrainslug_hip.so")
 
 BS_OK = 0
 BS_F32, BS_BF16 = 0, 1
-BS_BATCHNORM, BS_RELU, BS_ADD, BS_MAXPOOL, BS_AVGPOOL = 1, 2, 3, 4, 5
+BS_BATCHNORM, BS_RELU, BS_ADD, BS_MAXPOOL, BS_AVGPOOL, BS_LEAKY_RELU, BS_CLAMP = 1, 2, 3, 4, 5, 6, 7
 BS_VARIANT_AUTO, BS_VARIANT_STREAM, BS_VARIANT_POOL_DIRECT, BS_VARIANT_LDS_TILE = 0, 1, 2, 3
 BS_VARIANT_POOL_ROWS = 4
 VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows"}
@@ -38,7 +38,9 @@ class bs_layer_desc(C.Structure):
                 ("count_include_pad", C.c_int32), ("return_indices", C.c_int32),
                 ("ceil_mode", C.c_int32), ("dilation_h", C.c_int32), ("dilation_w", C.c_int32),
                 ("eps", C.c_double),
-                ("gamma", _f32p), ("beta", _f32p), ("running_mean", _f32p), ("running_var", _f32p)]
+                ("gamma", _f32p), ("beta", _f32p), ("running_mean", _f32p), ("running_var", _f32p),
+                ("negative_slope", C.c_float), ("clamp_min", C.c_float), ("clamp_max", C.c_float),
+                ("reserved", C.c_float)]
 
 
 class bs_plan_options(C.Structure):
@@ -185,6 +187,12 @@ def _marshal_layers(layers, channels):
             d.kind = BS_RELU
         elif kind == "add":
             d.kind = BS_ADD
+        elif kind == "leaky_relu":
+            d.kind = BS_LEAKY_RELU
+            d.negative_slope = float(l["slope"])
+        elif kind == "clamp":
+            d.kind = BS_CLAMP
+            d.clamp_min, d.clamp_max = float(l["lo"]), float(l["hi"])
         elif kind in ("maxpool", "avgpool"):
             d.kind = BS_MAXPOOL if kind == "maxpool" else BS_AVGPOOL
             d.kh, d.kw = l["k"]

@@ -27,7 +27,13 @@ enum OpKind : int32_t {
     OP_MAXPOOL = 4,
     OP_AVGSUM = 5,   // non-element-wise: window sum
     OP_AVGNORM = 6,  // element-wise: multiply by 1/divisor
+    OP_LEAKY = 7,    // element-wise: x > 0 ? x : x * slope
+    OP_CLAMP = 8,    // element-wise: min(max(x, lo), hi)
 };
+
+// Element-wise lists are packed into template arguments one base-K_EW_BASE digit per operation
+// (the operation kind; first operation in the lowest digit, 0 = end).
+constexpr int K_EW_BASE = 16;
 
 inline bool op_is_elementwise(int32_t k) { return k != OP_MAXPOOL && k != OP_AVGSUM; }
 
@@ -50,8 +56,9 @@ struct FastDiv {
 };
 
 struct EwOp {
-    int32_t kind;  // OP_BN, OP_RELU, OP_ADD
-    int32_t arg;   // BN: offset of scale[] in the parameter table; Add: residual slot of the sequence
+    int32_t kind;  // OP_BN, OP_RELU, OP_ADD, OP_LEAKY, OP_CLAMP
+    int32_t arg;   // BN: offset of scale[] in the parameter table (shift[] follows); leaky ReLU / clamp:
+                   // offset of [slope] / [lo, hi] there; Add: residual slot of the sequence
 };
 
 struct PoolK {

@@ -60,6 +60,19 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) x[u][i] = __builtin_fmaxf(x[u][i], 0.0f);  // NaN, -0 -> +0
+        } else if (kind == OP_LEAKY) {
+            const float slope = params[arg];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<BF16>(x[u][i] > 0.0f ? x[u][i] : x[u][i] * slope);
+        } else if (kind == OP_CLAMP) {
+            const float lo = params[arg], hi = params[arg + 1];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i)  // v_max / v_min: a NaN becomes lo
+                    x[u][i] = round_store<BF16>(__builtin_fminf(__builtin_fmaxf(x[u][i], lo), hi));
         } else {  // OP_ADD
             const void *rp = res[arg];
             Raw<BF16, VEC> rr[U];

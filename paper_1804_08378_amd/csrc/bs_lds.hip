@@ -18,14 +18,14 @@ using Max2s2p0 = PoolSpec<OP_MAXPOOL, 2, 2, 2, 2, 0, 0, 1>;
 using Avg2s2p0 = PoolSpec<OP_AVGSUM, 2, 2, 2, 2, 0, 0, 1>;
 
 constexpr int EW_NONE = 0;
-constexpr int EW_BN_RELU = OP_BN + 4 * OP_RELU;
+constexpr int EW_BN_RELU = OP_BN + K_EW_BASE * OP_RELU;
 
 static int ew_code(const LevelK &lv)
 {
     int code = 0, mul = 1;
     for (int j = 0; j < lv.n_ew; ++j) {
         code += lv.ew[j].kind * mul;
-        mul *= 4;
+        mul *= K_EW_BASE;
     }
     return code;
 }

@@ -66,8 +66,8 @@ struct PoolDyn {
     BS_DEV float inv_kk() const { return p.inv_kk; }
 };
 
-// Element-wise list of a level: CODE packs up to K_MAX_EW operation kinds, base 4, first
-// operation in the lowest digit (1 = BatchNorm, 2 = ReLU, 3 = Add, 0 = end); CODE < 0: run time.
+// Element-wise list of a level: CODE packs up to K_MAX_EW operation kinds, base K_EW_BASE, first
+// operation in the lowest digit (the OpKind value; 0 = end); CODE < 0: run time.
 template <int CODE>
 struct EwList {
     static constexpr bool is_static = CODE >= 0;
@@ -75,7 +75,7 @@ struct EwList {
     __host__ __device__ static constexpr int count_static()
     {
         int n = 0, c = CODE < 0 ? 0 : CODE;
-        while (c) { ++n; c /= 4; }
+        while (c) { ++n; c /= K_EW_BASE; }
         return n;
     }
     static constexpr int slots = CODE >= 0 ? count_static() : K_MAX_EW;
@@ -84,13 +84,13 @@ struct EwList {
     {
         if (CODE >= 0) {
             int c = CODE;
-            for (int i = 0; i < j; ++i) c /= 4;
-            return c % 4;  // digits equal OP_BN / OP_RELU / OP_ADD
+            for (int i = 0; i < j; ++i) c /= K_EW_BASE;
+            return c % K_EW_BASE;  // digits are the operation kinds
         }
         return lv.ew[j].kind;
     }
 };
-static_assert(OP_BN == 1 && OP_RELU == 2 && OP_ADD == 3, "EwList digits are the operation kinds");
+static_assert(OP_CLAMP < K_EW_BASE, "EwList digits are the operation kinds");
 
 template <class P>
 BS_DEV float pad_value(const P &p) { return p.kind() == OP_MAXPOOL ? -INFINITY : 0.0f; }
@@ -111,9 +111,15 @@ BS_DEV void load_ew_regs(const LevelK &lv, const float *params, int32_t C, int32
     for (int j = 0; j < EW::slots; ++j) {
         e.sc[j] = 1.0f;
         e.sh[j] = 0.0f;
-        if (j < EW::count(lv) && EW::kind(lv, j) == OP_BN) {
-            e.sc[j] = cp[lv.ew[j].arg + c];
-            e.sh[j] = cp[lv.ew[j].arg + C + c];
+        if (j < EW::count(lv)) {
+            const int32_t kind = EW::kind(lv, j);
+            if (kind == OP_BN) {
+                e.sc[j] = cp[lv.ew[j].arg + c];
+                e.sh[j] = cp[lv.ew[j].arg + C + c];
+            } else if (kind == OP_LEAKY || kind == OP_CLAMP) {  // [slope, -] / [lo, hi]
+                e.sc[j] = cp[lv.ew[j].arg];
+                e.sh[j] = cp[lv.ew[j].arg + 1];
+            }
         }
     }
 }
@@ -135,6 +141,12 @@ BS_DEV void apply_level_ew(float (&x)[N], const LevelK &lv, const EwRegs<EW> &er
             // v_max_f32: NaN -> 0, and max(-0, +0) = +0 in either operand order
 #pragma unroll
             for (int i = 0; i < N; ++i) x[i] = __builtin_fmaxf(x[i], 0.0f);
+        } else if (kind == OP_LEAKY) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(x[i] > 0.0f ? x[i] : x[i] * er.sc[j]);
+        } else if (kind == OP_CLAMP) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fminf(__builtin_fmaxf(x[i], er.sc[j]), er.sh[j]));
         } else {
             const void *rp = res[lv.ew[j].arg];
             float r[N];

@@ -42,6 +42,20 @@ bs_status build_operations(bs_stack *s)
             op.kind = OP_RELU;
             s->ops.push_back(op);
             break;
+        case BS_LEAKY_RELU:
+            op.kind = OP_LEAKY;
+            op.param_off = (int32_t)s->host_params.size();
+            s->host_params.push_back(L.desc.negative_slope);
+            s->host_params.push_back(0.0f);
+            s->ops.push_back(op);
+            break;
+        case BS_CLAMP:
+            op.kind = OP_CLAMP;
+            op.param_off = (int32_t)s->host_params.size();
+            s->host_params.push_back(L.desc.clamp_min);
+            s->host_params.push_back(L.desc.clamp_max);
+            s->ops.push_back(op);
+            break;
         case BS_ADD:
             op.kind = OP_ADD;
             op.res_slot = res++;
@@ -336,7 +350,7 @@ static void fill_ew(const bs_stack *s, const Op &op, Sequence &q, EwOp &e)
 {
     e.kind = op.kind;
     e.arg = 0;
-    if (op.kind == OP_BN) e.arg = op.param_off;
+    if (op.kind == OP_BN || op.kind == OP_LEAKY || op.kind == OP_CLAMP) e.arg = op.param_off;
     if (op.kind == OP_ADD) {
         int32_t slot = -1;
         for (int32_t j = 0; j < q.n_res; ++j)
@@ -1157,6 +1171,8 @@ const char *bs_stack_operation_name(const bs_stack *stack, int32_t op)
     case OP_MAXPOOL: return "MaxPooling";
     case OP_AVGSUM: return "AvgPooling";
     case OP_AVGNORM: return "AvgNormalization";
+    case OP_LEAKY: return "LeakyReLU";
+    case OP_CLAMP: return "Clamp";
     }
     return nullptr;
 }

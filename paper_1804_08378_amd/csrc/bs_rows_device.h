@@ -10,26 +10,26 @@ struct RowsSpec {
     static constexpr int kind = KIND, kh = KH, kw = KW, sh = SH, sw = SW, ph = PH, pw = PW;
 };
 
-// element-wise list codes (base 4 digits, first operation lowest): see rows_ew_code()
+// element-wise list codes (base K_EW_BASE digits, first operation lowest): see rows_ew_code()
 constexpr int K_ROWS_OR = 2;  // output rows per lane per iteration (all their input rows are requested at once)
 constexpr int RW_NONE = 0;
 constexpr int RW_RELU = OP_RELU;
-constexpr int RW_BN_RELU = OP_BN + 4 * OP_RELU;
+constexpr int RW_BN_RELU = OP_BN + K_EW_BASE * OP_RELU;
 
 template <int CODE>
 struct RowsEw {
     static constexpr int count()
     {
         int n = 0, c = CODE;
-        while (c) { ++n; c /= 4; }
+        while (c) { ++n; c /= K_EW_BASE; }
         return n;
     }
     static constexpr int n = count();
     __host__ __device__ static constexpr int kind(int j)
     {
         int c = CODE;
-        for (int i = 0; i < j; ++i) c /= 4;
-        return c % 4;
+        for (int i = 0; i < j; ++i) c /= K_EW_BASE;
+        return c % K_EW_BASE;
     }
 };
 
@@ -49,12 +49,14 @@ BS_DEV void rows_load_params(const EwOp *ew, const float *__restrict__ params, i
         if (EW::kind(j) == OP_BN) {
             p.sc[j] = params[ew[j].arg + c];
             p.sh[j] = params[ew[j].arg + C + c];
+        } else if (EW::kind(j) == OP_LEAKY || EW::kind(j) == OP_CLAMP) {  // [slope, -] / [lo, hi]
+            p.sc[j] = params[ew[j].arg];
+            p.sh[j] = params[ew[j].arg + 1];
         }
     }
 }
 
-// BatchNorm / ReLU lists only (a residual Add would need its own halo loads; such stacks
-// take the LDS path).
+// Lists without a residual Add (it would need its own halo loads; such stacks take the LDS path).
 template <bool BF16, class EW, int N>
 BS_DEV void rows_apply(float (&x)[N], const RowsParams<EW> &p)
 {
@@ -63,6 +65,12 @@ BS_DEV void rows_apply(float (&x)[N], const RowsParams<EW> &p)
         if (EW::kind(j) == OP_BN) {
 #pragma unroll
             for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fmaf(x[i], p.sc[j], p.sh[j]));
+        } else if (EW::kind(j) == OP_LEAKY) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(x[i] > 0.0f ? x[i] : x[i] * p.sc[j]);
+        } else if (EW::kind(j) == OP_CLAMP) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fminf(__builtin_fmaxf(x[i], p.sc[j]), p.sh[j]));
         } else {
 #pragma unroll
             for (int i = 0; i < N; ++i) x[i] = __builtin_fmaxf(x[i], 0.0f);  // NaN, -0 -> +0
@@ -75,14 +83,14 @@ using RMax3s2p0 = RowsSpec<OP_MAXPOOL, 3, 3, 2, 2, 0, 0>;
 using RMax3s1p1 = RowsSpec<OP_MAXPOOL, 3, 3, 1, 1, 1, 1>;
 using RAvg3s1p1 = RowsSpec<OP_AVGSUM, 3, 3, 1, 1, 1, 1>;
 
-// base-4 code of a BatchNorm / ReLU list (first operation lowest digit), -1 for other lists
+// code of an element-wise list without residual Add (first operation lowest digit), -1 otherwise
 inline int rows_ew_code(const EwOp *ew, int n)
 {
     int code = 0, mul = 1;
     for (int j = 0; j < n; ++j) {
-        if (ew[j].kind != OP_BN && ew[j].kind != OP_RELU) return -1;
+        if (ew[j].kind == OP_ADD) return -1;
         code += ew[j].kind * mul;
-        mul *= 4;
+        mul *= K_EW_BASE;
     }
     return code;
 }

@@ -100,6 +100,15 @@ bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers, const i
             }
             case BS_RELU:
                 break;
+            case BS_LEAKY_RELU:
+                if (!std::isfinite(d.negative_slope)) { err = BS_ERR_PARAM; break; }
+                break;
+            case BS_CLAMP:
+                if (!std::isfinite(d.clamp_min) || !std::isfinite(d.clamp_max) || d.clamp_min > d.clamp_max) {
+                    err = BS_ERR_PARAM;
+                    break;
+                }
+                break;
             case BS_ADD:
                 if (s->n_res >= BS_MAX_RESIDUALS) { err = BS_ERR_UNSUPPORTED; break; }
                 std::memcpy(s->res_shape[s->n_res++], cur, sizeof(cur));

@@ -1,7 +1,8 @@
 """PyTorch front-end: aggregation detection and model rewriting (Sections 4 and 4.3, Figure 4).
 
 `optimize(model)` scans the layers of every `torch.nn.Sequential` in the model in order, pushes
-consecutive optimizable layers (inference BatchNorm2d, ReLU, MaxPool2d, AvgPool2d, and the layers
+consecutive optimizable layers (inference BatchNorm2d, ReLU, LeakyReLU, ReLU6, Hardtanh, MaxPool2d,
+AvgPool2d, and the layers
 that are the identity at inference time) on a stack, and when it meets a layer it cannot optimize
 (a convolution, a linear layer, ...) collapses the stack: the first layer of the run is replaced
 by a `BrainSlugStack` module that executes the whole run depth-first through the C ABI, the
@@ -49,6 +50,12 @@ def layer_desc(m: nn.Module) -> Optional[dict]:
                 "mean": f(m.running_mean, zeros), "var": f(m.running_var, ones), "eps": float(m.eps)}
     if isinstance(m, nn.ReLU):
         return {"kind": "relu"}
+    if isinstance(m, nn.LeakyReLU):
+        return {"kind": "leaky_relu", "slope": float(m.negative_slope)}
+    if isinstance(m, nn.ReLU6):
+        return {"kind": "clamp", "lo": 0.0, "hi": 6.0}
+    if isinstance(m, nn.Hardtanh):
+        return {"kind": "clamp", "lo": float(m.min_val), "hi": float(m.max_val)}
     if isinstance(m, nn.MaxPool2d):
         if _pair(m.dilation) != (1, 1) or m.return_indices:
             return None  # a Sequential cannot pass on the (values, indices) pair anyway

@@ -43,6 +43,8 @@ def test_create_rejects_bad_arguments():
     assert _status(bs.bs_stack_create, [wl.maxpool(2, 2, 2)], (1, 4, 8, 8), "f32") == 3  # p > k/2
     assert _status(bs.bs_stack_create, [wl.maxpool(0, 1, 0)], (1, 4, 8, 8), "f32") == 3
     assert _status(bs.bs_stack_create, [wl.avgpool(2, 0, 0)], (1, 4, 8, 8), "f32") == 3
+    assert _status(bs.bs_stack_create, [wl.clamp(1.0, 0.0)], (1, 4, 8, 8), "f32") == 3       # lo > hi
+    assert _status(bs.bs_stack_create, [wl.leaky_relu(float("nan"))], (1, 4, 8, 8), "f32") == 3
     h = bs.bs_stack_create([wl.maxpool(2, 2, ceil_mode=True)], (1, 4, 9, 9), "f32")  # ceil mode: 5 x 5 outputs
     assert bs.bs_stack_output_shape(h) == (1, 4, 5, 5)
     bs.bs_stack_destroy(h)

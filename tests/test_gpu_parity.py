@@ -338,6 +338,37 @@ def test_run_time_builds(shape, dtype):
         check(layers, x, res, dtype, f"built/{name}{shape}/off", jit=-1)
 
 
+# ------------------------------------------------------------------ further activations
+def _activation_stacks(c):
+    return {
+        "stream": ([wl.bn_params(c, 93), wl.leaky_relu(0.1), wl.add(), wl.relu6()], 1),
+        "direct": ([wl.bn_params(c, 94), wl.relu6(), wl.maxpool(2, 2, 0, True), wl.leaky_relu(0.2)], 0),
+        "rows": ([wl.bn_params(c, 95), wl.leaky_relu(0.01), wl.maxpool(3, 2, 1, True), wl.clamp(-0.5, 1.5)], 0),
+        "rows2": ([wl.clamp(-1.0, 1.0), wl.avgpool(3, 1, 1), wl.leaky_relu(0.3), wl.maxpool(3, 2, 1, True),
+                   wl.bn_params(c, 96), wl.relu6()], 0),
+        "lds": ([wl.leaky_relu(0.1), wl.maxpool(3, 1, 1, True), wl.bn_params(c, 97), wl.add(), wl.relu6(),
+                 wl.avgpool(2, 2, 0), wl.clamp(0.25, 0.75), wl.maxpool(3, 1, 1)], 1),
+    }
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 24, 32), (1, 2, 31, 30)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_leaky_relu_and_clamp_in_every_kernel_family(shape, dtype):
+    for name, (layers, n_res) in _activation_stacks(shape[1]).items():
+        x = wl.activation(shape, 75, dtype) * 3
+        res = []
+        if n_res:
+            rshape = wl.output_shape(layers[:[l["kind"] for l in layers].index("add")], shape)
+            res = [wl.activation(rshape, 76, dtype)]
+        x = np.ascontiguousarray(x.astype(np.float32))
+        if dtype == "bf16":
+            from oracle import layers as OL
+            x = OL.round_bf16(x)
+        check(layers, x, res, dtype, f"act/{name}{shape}")
+        check(layers, x, res, dtype, f"act/{name}{shape}/layer-by-layer", breadth_first=1)
+        check(layers, x, res, dtype, f"act/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
+
+
 # ------------------------------------------------------------------ ceil mode
 def _ceil_stacks(c):
     return {
