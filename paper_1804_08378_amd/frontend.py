@@ -2,7 +2,7 @@
 
 `optimize(model)` scans the layers of every `torch.nn.Sequential` in the model in order, pushes
 consecutive optimizable layers (inference BatchNorm2d, ReLU, LeakyReLU, ReLU6, Hardtanh, MaxPool2d,
-AvgPool2d, and the layers
+AvgPool2d, adaptive pools whose output size divides their input, and the layers
 that are the identity at inference time) on a stack, and when it meets a layer it cannot optimize
 (a convolution, a linear layer, ...) collapses the stack: the first layer of the run is replaced
 by a `BrainSlugStack` module that executes the whole run depth-first through the C ABI, the
@@ -29,8 +29,9 @@ import torch
 from torch import nn
 
 from . import brainslug as bs
+from . import workloads as wl
 
-__all__ = ["optimize", "BrainSlugStack", "layer_desc", "find_runs"]
+__all__ = ["optimize", "BrainSlugStack", "layer_desc", "find_runs", "resolve_layers"]
 
 
 def _pair(v) -> Tuple[int, int]:
@@ -69,6 +70,13 @@ def layer_desc(m: nn.Module) -> Optional[dict]:
         return {"kind": "avgpool", "k": k, "s": _pair(m.stride if m.stride is not None else k),
                 "p": _pair(m.padding), "count_include_pad": bool(m.count_include_pad),
                 "ceil_mode": bool(m.ceil_mode)}
+    if isinstance(m, (nn.AdaptiveAvgPool2d, nn.AdaptiveMaxPool2d)):
+        if getattr(m, "return_indices", False):
+            return None
+        out = m.output_size if isinstance(m.output_size, (tuple, list)) else (m.output_size, m.output_size)
+        # resolved to a fixed pool when the input size is known (plan_for): an adaptive pool whose
+        # input size is a multiple of its output size is a pool with k = s = in / out
+        return {"kind": "adaptive_avg" if isinstance(m, nn.AdaptiveAvgPool2d) else "adaptive_max", "out": tuple(out)}
     if isinstance(m, (nn.Identity, nn.Dropout, nn.Dropout2d)):
         return {}  # identity at inference time
     return None
@@ -90,6 +98,28 @@ def find_runs(seq: nn.Sequential) -> List[Tuple[int, int]]:
                 start = i
             real += 1 if d else 0
     return runs
+
+
+def resolve_layers(layers: List[dict], shape) -> List[dict]:
+    """Concrete layer list for an input of `shape`: adaptive pools become fixed pools."""
+    h, w = int(shape[2]), int(shape[3])
+    out = []
+    for l in layers:
+        if l["kind"] in ("adaptive_avg", "adaptive_max"):
+            oh = h if l["out"][0] is None else int(l["out"][0])
+            ow = w if l["out"][1] is None else int(l["out"][1])
+            if oh < 1 or ow < 1 or h % oh or w % ow:
+                raise RuntimeError(f"adaptive pooling of a {h}x{w} plane to {oh}x{ow}: only sizes that divide "
+                                   "the input are supported")
+            k = (h // oh, w // ow)
+            l = ({"kind": "avgpool", "k": k, "s": k, "p": (0, 0), "count_include_pad": True}
+                 if l["kind"] == "adaptive_avg" else
+                 {"kind": "maxpool", "k": k, "s": k, "p": (0, 0), "return_indices": False})
+        if l["kind"] in ("maxpool", "avgpool"):
+            h = wl.pool_out(h, l["k"][0], l["s"][0], l["p"][0], l.get("ceil_mode", False))
+            w = wl.pool_out(w, l["k"][1], l["s"][1], l["p"][1], l.get("ceil_mode", False))
+        out.append(l)
+    return out
 
 
 class BrainSlugStack(nn.Module):
@@ -116,7 +146,7 @@ class BrainSlugStack(nn.Module):
             name = {torch.float32: "f32", torch.bfloat16: "bf16"}.get(dtype)
             if name is None:
                 raise TypeError(f"BrainSlugStack supports float32 and bfloat16 tensors, not {dtype}")
-            st = bs.Stack(self.layers, key[0], name).plan(**self.plan_opts)
+            st = bs.Stack(resolve_layers(self.layers, key[0]), key[0], name).plan(**self.plan_opts)
             self._plans[key] = st
         return st
 

@@ -114,7 +114,54 @@ def test_extracted_layer_descriptions_reproduce_the_torch_model(shape):
             st.close()
 
 
+def head_like(c=8, seed=1):
+    """The tail of a DenseNet / ResNet style network written as modules."""
+    torch.manual_seed(seed)
+    m = nn.Sequential(nn.Conv2d(3, c, 3, padding=1), nn.BatchNorm2d(c), nn.LeakyReLU(0.1), nn.MaxPool2d(3, 2, ceil_mode=True),
+                      nn.ReLU6(), nn.AdaptiveAvgPool2d(1), nn.Flatten(), nn.Linear(c, 5))
+    bn = m[1]
+    bn.running_mean.copy_(torch.randn(c) * 0.5)
+    bn.running_var.copy_(torch.rand(c) + 0.5)
+    return m.eval()
+
+
+def test_adaptive_pools_ceil_mode_and_further_activations_are_taken():
+    ref = head_like()
+    assert fe.find_runs(ref) == [(1, 6)]
+    opt = fe.optimize(copy.deepcopy(ref))
+    stack = opt.optimized_stacks[0]
+    assert [l["kind"] for l in stack.layers] == ["bn", "leaky_relu", "maxpool", "clamp", "adaptive_avg"]
+    x = torch.randn(2, 3, 14, 18)
+    with torch.no_grad():
+        xin = ref[:1](x)
+        want = ref[1:6](xin).numpy()
+    layers = fe.resolve_layers(stack.layers, xin.shape)
+    assert layers[-1] == {"kind": "avgpool", "k": (7, 9), "s": (7, 9), "p": (0, 0), "count_include_pad": True}
+    got, _, _ = bf.run_stack(layers, np.ascontiguousarray(xin.numpy()))
+    assert got.shape == want.shape == (2, 8, 1, 1)
+    assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(want).max())
+    with pytest.raises(RuntimeError, match="divide"):
+        fe.resolve_layers([{"kind": "adaptive_avg", "out": (3, 3)}], (1, 1, 7, 7))
+
+
 # ------------------------------------------------------------------ GPU
+@pytest.mark.gpu
+def test_head_like_model_on_the_gpu():
+    ref = head_like(c=16).cuda()
+    opt = fe.optimize(copy.deepcopy(ref))
+    x = torch.randn(3, 3, 30, 34, device="cuda")
+    with torch.no_grad():
+        want, got = ref(x), opt(x)
+        xin = ref[:1](x)
+    assert (got - want).abs().max().item() <= 1e-4 * max(1.0, want.abs().max().item())
+    stack = opt.optimized_stacks[0]
+    expect, _, _ = bf.run_stack(fe.resolve_layers(stack.layers, xin.shape), xin.cpu().numpy())
+    with torch.no_grad():
+        out = stack(xin)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+    stack.close()
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_rewritten_model_matches_the_original_and_the_oracle(dtype):
