@@ -125,7 +125,8 @@ typedef enum bs_variant {
     BS_VARIANT_STREAM = 1,      /* element-wise only: 128-bit streaming, registers only         */
     BS_VARIANT_POOL_DIRECT = 2, /* one step, disjoint windows (k == s, p == 0): registers only   */
     BS_VARIANT_LDS_TILE = 3,    /* tiles with halos staged in LDS, ping-pong buffers, barriers   */
-    BS_VARIANT_POOL_ROWS = 4    /* one or two pooling steps with overlapping / padded windows: rows slide in registers, no LDS */
+    BS_VARIANT_POOL_ROWS = 4,   /* one or two pooling steps with overlapping / padded windows: rows slide in registers, no LDS */
+    BS_VARIANT_PLANE_POOL = 5   /* one step whose window is the whole (small) plane: one lane per plane       */
 } bs_variant;
 
 /*

@@ -20,8 +20,8 @@ BS_OK = 0
 BS_F32, BS_BF16 = 0, 1
 BS_BATCHNORM, BS_RELU, BS_ADD, BS_MAXPOOL, BS_AVGPOOL, BS_LEAKY_RELU, BS_CLAMP = 1, 2, 3, 4, 5, 6, 7
 BS_VARIANT_AUTO, BS_VARIANT_STREAM, BS_VARIANT_POOL_DIRECT, BS_VARIANT_LDS_TILE = 0, 1, 2, 3
-BS_VARIANT_POOL_ROWS = 4
-VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows"}
+BS_VARIANT_POOL_ROWS, BS_VARIANT_PLANE_POOL = 4, 5
+VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows", 5: "plane_pool"}
 STATUS_NAMES = {
     0: "BS_OK", 1: "BS_ERR_NULL", 2: "BS_ERR_SHAPE", 3: "BS_ERR_PARAM", 4: "BS_ERR_UNSUPPORTED",
     5: "BS_ERR_NOT_PLANNED", 6: "BS_ERR_NO_FIT", 7: "BS_ERR_ALIGN", 8: "BS_ERR_WORKSPACE",

@@ -257,6 +257,56 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 }
 
 // =============================================================================
+// plane_pool_kernel: [element-wise]* pool(window = the whole plane) [element-wise]*, the
+// global pooling at the end of a network.  One lane per plane walks the plane in row-major
+// order (the order in which the average's sum and the first-maximum rule are defined), eight
+// elements requested at a time; planes are small here (the planner sends large ones to the
+// tile kernels).  A plane is contiguous, so a lane's loads fall into a few cache lines.
+// =============================================================================
+template <bool BF16>
+__global__ __launch_bounds__(256) void plane_pool_kernel(const PoolDirectK k)
+{
+    constexpr int U = 8;
+    uint32_t plane = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = plane < k.total;
+    plane = live ? plane : 0u;
+    const int32_t c1[1] = {(int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C)};
+    const uint32_t hw = (uint32_t)(k.H * k.W), base = plane * hw;
+    const bool is_max = k.pool.kind == OP_MAXPOOL;
+    float acc = is_max ? -INFINITY : 0.0f;
+    int32_t bi = 0;  // first cell of the plane
+    for (uint32_t i0 = 0; i0 < hw; i0 += U) {
+        Raw<BF16, 1> raw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) raw[u] = load_raw<BF16, 1>(k.in, base + min(i0 + u, hw - 1));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float x[1][1];
+            unpack<BF16, 1>(raw[u], x[0]);
+            const uint32_t o1[1] = {base + min(i0 + u, hw - 1)};
+            apply_ew<BF16, 1, 1>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
+            const float v = x[0][0];
+            if (i0 + u < hw) {
+                if (is_max) {
+                    const bool g = v > acc;
+                    acc = g ? v : acc;
+                    bi = g ? (int32_t)(i0 + u) : bi;
+                } else {
+                    acc = acc + v;
+                }
+            }
+        }
+    }
+    float y[1][1] = {{is_max ? acc : round_store<BF16>(acc * k.pool.inv_kk)}};
+    const uint32_t oo[1] = {plane};  // Ho = Wo = 1: the output (and a residual of its shape) is indexed by plane
+    apply_ew<BF16, 1, 1>(y, c1, oo, k.post, k.n_post, k.params, k.C, k.res);
+    if (live) {
+        store_elems<BF16, 1>(k.out, plane, y[0]);
+        if (k.idx && is_max) k.idx[plane] = bi;
+    }
+}
+
+// =============================================================================
 // Host side: device queries, parameter upload, launchers.
 // =============================================================================
 static bs_status hip_fail(hipError_t e)
@@ -376,6 +426,15 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.idx = ip[0];
         if (bf16) launch_direct<true, 8>(k, grid, block, st);
         else launch_direct<false, 4>(k, grid, block, st);
+        break;
+    }
+    case BS_VARIANT_PLANE_POOL: {
+        PoolDirectK k = q.direct;
+        k.in = in; k.out = out; k.params = s->dev_params;
+        for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
+        k.idx = ip[0];
+        if (bf16) plane_pool_kernel<true><<<grid, block, 0, st>>>(k);
+        else plane_pool_kernel<false><<<grid, block, 0, st>>>(k);
         break;
     }
     case BS_VARIANT_POOL_ROWS: {

@@ -321,12 +321,14 @@ static bool direct_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops
 // Resource consumption of a candidate sequence (Section 4.1): the on-chip bytes of the
 // smallest useful tile, including the overlap that padding / k > s adds at every level.
 static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill);
+static bool plane_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops);
 
 static uint64_t seq_min_lds(const bs_stack *s, int32_t first_op, int32_t n_ops, int32_t threads)
 {
     if (count_pools(s, first_op, n_ops) == 0) return 0;
     if (direct_applicable(s, first_op, n_ops) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
     if (rows_applicable(s, first_op, n_ops, nullptr) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
+    if (plane_applicable(s, first_op, n_ops) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
     const Op &last = s->ops[first_op + n_ops - 1];
     int32_t th, tw;
     min_tile(last.out_h, last.out_w, threads, th, tw);
@@ -403,9 +405,29 @@ static void plan_stream(const bs_stack *s, Sequence &q)
     q.planes_per_group = 0;
 }
 
-static void plan_direct(const bs_stack *s, Sequence &q)
+// One pooling operation whose window is the whole plane (global pooling), the plane small
+// enough for one lane to walk it.
+static bool plane_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops)
 {
-    q.variant = BS_VARIANT_POOL_DIRECT;
+    if (count_pools(s, first_op, n_ops) != 1) return false;
+    int32_t pre = 0, post = 0;
+    bool seen = false;
+    for (int32_t i = first_op; i < first_op + n_ops; ++i) {
+        const Op &op = s->ops[i];
+        if (!op_is_elementwise(op.kind)) {
+            if (op.kh != op.in_h || op.kw != op.in_w || op.ph != 0 || op.pw != 0) return false;
+            if (op.out_h != 1 || op.out_w != 1 || (int64_t)op.in_h * op.in_w > 1024) return false;
+            seen = true;
+        } else if (op.kind != OP_AVGNORM) {
+            (seen ? post : pre)++;
+        }
+    }
+    return pre <= K_MAX_EW && post <= K_MAX_EW;
+}
+
+static void plan_direct(const bs_stack *s, Sequence &q, bool whole_plane = false)
+{
+    q.variant = whole_plane ? BS_VARIANT_PLANE_POOL : BS_VARIANT_POOL_DIRECT;
     PoolDirectK &k = q.direct;
     k = PoolDirectK{};
     const int32_t vec = vec_of(s);
@@ -424,6 +446,19 @@ static void plan_direct(const bs_stack *s, Sequence &q)
     }
     k.C = (int32_t)q.in_shape[1];
     const int64_t planes = q.in_shape[0] * q.in_shape[1];
+    if (whole_plane) {
+        q.vec = 1;
+        k.total = (uint32_t)planes;
+        k.div_c = make_fastdiv((uint32_t)k.C);
+        q.threads = std::min(q.threads, 256);
+        q.grid = (planes + q.threads - 1) / q.threads;
+        q.lds_bytes = 0;
+        q.redundancy = 1.0;
+        q.tile_rows = q.tile_cols = 1;
+        q.planes_per_group = q.threads;
+        q.n_levels = 1;
+        return;
+    }
     const int32_t wv = k.W / vec;
     k.total = (uint32_t)(planes * k.Ho * wv);
     k.div_wv = make_fastdiv((uint32_t)wv);
@@ -628,7 +663,9 @@ static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, 
 static bool seq_is_fast(const bs_stack *s, int32_t first_op, int32_t n_ops)
 {
     if (count_pools(s, first_op, n_ops) == 0) return true;
-    if (direct_applicable(s, first_op, n_ops) || rows_applicable(s, first_op, n_ops, nullptr)) return true;
+    if (direct_applicable(s, first_op, n_ops) || rows_applicable(s, first_op, n_ops, nullptr) ||
+        plane_applicable(s, first_op, n_ops))
+        return true;
     if (!seq_capacity_ok(s, first_op, n_ops, false)) return false;
     if (jit_allowed(s)) return true;  // any signature gets its own build
     Sequence tmp;
@@ -990,6 +1027,8 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             plan_direct(s, q);
         } else if (rows_applicable(s, q.first_op, q.n_ops, nullptr) && o.force_variant != BS_VARIANT_LDS_TILE) {
             plan_rows(s, q, o, lim);
+        } else if (plane_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {
+            plan_direct(s, q, true);
         } else {
             st = plan_lds(s, q, o, lim);
         }
@@ -1025,7 +1064,7 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (o.threads_per_group != 0 &&
         (o.threads_per_group < 64 || o.threads_per_group > 512 || o.threads_per_group % 64 != 0))
         return BS_ERR_PARAM;
-    if (o.force_variant < 0 || o.force_variant > BS_VARIANT_POOL_ROWS) return BS_ERR_PARAM;
+    if (o.force_variant < 0 || o.force_variant > BS_VARIANT_PLANE_POOL) return BS_ERR_PARAM;
     if (o.max_lds_bytes > 64 * 1024) return BS_ERR_PARAM;
     if (o.jit < -1 || o.jit > 1) return BS_ERR_PARAM;
 

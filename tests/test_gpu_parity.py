@@ -338,6 +338,28 @@ def test_run_time_builds(shape, dtype):
         check(layers, x, res, dtype, f"built/{name}{shape}/off", jit=-1)
 
 
+# ------------------------------------------------------------------ global pooling
+@pytest.mark.parametrize("shape", [(3, 5, 7, 7), (2, 4, 1, 1), (1, 300, 6, 5), (2, 3, 13, 9)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_global_pooling_one_lane_per_plane(shape, dtype):
+    """Pools whose window is the whole plane (the head of a network): average and maximum with
+    indices, element-wise layers (a residual Add among them) before and after."""
+    h, w = shape[2], shape[3]
+    x = wl.activation(shape, 77, dtype)
+    out_shape = shape[:2] + (1, 1)
+    stacks = {
+        "avg_head": ([wl.bn_params(shape[1], 98), wl.relu(), wl.avgpool((h, w), (h, w), 0)], []),
+        "max_head": ([wl.leaky_relu(0.1), wl.maxpool((h, w), (1, 1), 0, True), wl.bn_params(shape[1], 99)], []),
+        "residuals": ([wl.add(), wl.relu(), wl.avgpool((h, w), (h, w), 0, False), wl.add(), wl.relu6()],
+                      [wl.activation(shape, 78, dtype), wl.activation(out_shape, 79, dtype)]),
+    }
+    for name, (layers, res) in stacks.items():
+        info = check(layers, x, res, dtype, f"global/{name}{shape}")
+        if h * w > 4:
+            assert info["sequences"][0]["variant_name"] in ("plane_pool", "pool_rows"), name
+        check(layers, x, res, dtype, f"global/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
+
+
 # ------------------------------------------------------------------ further activations
 def _activation_stacks(c):
     return {
