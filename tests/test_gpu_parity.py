@@ -338,6 +338,54 @@ def test_run_time_builds(shape, dtype):
         check(layers, x, res, dtype, f"built/{name}{shape}/off", jit=-1)
 
 
+# ------------------------------------------------------------------ HIP graph capture
+def test_run_can_be_captured_in_a_hip_graph_and_replayed():
+    """bs_stack_run only enqueues kernels on the caller's stream (no allocation, no
+    synchronisation, no memset), so a whole multi-sequence stack -- pre-compiled kernels and one
+    built at plan time -- can be captured once and replayed; every replay, with new input
+    contents and eager work in between, matches the oracle."""
+    c = 6
+    layers = ([wl.bn_params(c, 40), wl.relu(), wl.maxpool(2, 2, 0, True)] +
+              sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 41 + i), wl.relu()] for i in range(7)), []) +
+              [wl.maxpool(5, 1, 2), wl.leaky_relu(0.1), wl.add(), wl.avgpool(2, 2, 0)])
+    shape = (2, c, 32, 48)
+    st = bs.Stack(layers, shape, "f32").plan()
+    info = st.info()
+    assert info["n_sequences"] >= 2 and info["workspace_bytes"] > 0
+    assert any(q["run_time_build"] for q in info["sequences"])
+    rshape = (2, c, 16, 24)
+    x_static = torch.zeros(shape, device="cuda")
+    r_static = torch.zeros(rshape, device="cuda")
+    out, idx = st.alloc_outputs("cuda", True)
+    st.workspace("cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st.run(x_static, [r_static], out=out, indices=idx)  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        st.run(x_static, [r_static], out=out, indices=idx)
+    for rep in range(3):
+        x = wl.activation(shape, 50 + rep)
+        r = wl.activation(rshape, 60 + rep)
+        x_static.copy_(torch.from_numpy(x))
+        r_static.copy_(torch.from_numpy(r))
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref, ref_idx, _ = bf.run_stack(layers, x, [r])
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32)), rep
+        assert np.array_equal(idx[0].cpu().numpy(), ref_idx[0]), rep
+        # eager launch of the same stack between replays
+        o2, _ = st.run(x_static, [r_static])
+        torch.cuda.synchronize()
+        assert torch.equal(o2, out)
+    del graph
+    st.close()
+
+
 # ------------------------------------------------------------------ global pooling
 @pytest.mark.parametrize("shape", [(3, 5, 7, 7), (2, 4, 1, 1), (1, 300, 6, 5), (2, 3, 13, 9)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
