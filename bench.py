@@ -67,15 +67,18 @@ class StackBench:
         self.cursor = 0
         self.info = self.fused.info()
 
-    def launch(self, which="fused"):
+    def launch(self, which="fused", stream=None):
         s = self.cursor
         self.cursor = (self.cursor + 1) % self.sets
         st = self.fused if which == "fused" else self.lbl
-        st.run(self.x[s], self.res[s], out=self.out[s], indices=self.idx[s])
+        st.run(self.x[s], self.res[s], out=self.out[s], indices=self.idx[s],
+               stream=None if stream is None else stream.cuda_stream)
 
 
-def time_steps(stacks, which, steps, warmup):
-    """K steps (each: every stack once, rotating buffers).
+def time_steps(stacks, which, steps, warmup, streams=None):
+    """K steps (each: every stack once, rotating buffers).  With `streams` (one HIP stream of
+    default priority per stack) the stacks of a step, which are independent of each other, are
+    enqueued on their own streams, so the tail of one kernel overlaps the start of the next.
 
     Returns (wall ms per step, {name: mean ms}, {name: min ms}).  The wall time brackets exactly
     `steps` steps with a device synchronisation on both sides and nothing else in between; the
@@ -84,14 +87,15 @@ def time_steps(stacks, which, steps, warmup):
     """
     import torch
 
+    streams = streams or [None] * len(stacks)
     for _ in range(warmup):
-        for sb in stacks:
-            sb.launch(which)
+        for sb, st in zip(stacks, streams):
+            sb.launch(which, st)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        for sb in stacks:
-            sb.launch(which)
+        for sb, st in zip(stacks, streams):
+            sb.launch(which, st)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ev = {sb.name: [] for sb in stacks}
@@ -267,6 +271,9 @@ def main():
     ap.add_argument("--deep", action="store_true",
                     help="also run the stacked-layers experiment of Section 5.1: 1..40 blocks of "
                          "<MaxPool 3/1/1, BatchNorm, ReLU> under the three sequence strategies")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="enqueue all stacks of a step on one stream (default: the three independent stacks "
+                         "of a step go to one HIP stream each, all of default priority)")
     ap.add_argument("--frontend", action="store_true",
                     help="also time the VGG stacks as torch modules: PyTorch eager against frontend.optimize()")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
@@ -305,11 +312,12 @@ def main():
 
     stacks = [StackBench(n, "f32") for n in wl.VGG_STACKS]
     step_bytes = sum(sb.bytes for sb in stacks)
-    ms, per, mins = time_steps(stacks, "fused", args.steps, args.warmup)
+    streams = None if args.one_stream else [torch.cuda.Stream() for _ in stacks]
+    ms, per, mins = time_steps(stacks, "fused", args.steps, args.warmup, streams)
     if args.no_baseline:
         ms_lbl = float("nan")
     else:
-        ms_lbl, per_lbl, _ = time_steps(stacks, "lbl", max(10, args.steps // 4), max(2, args.warmup // 2))
+        ms_lbl, per_lbl, _ = time_steps(stacks, "lbl", max(10, args.steps // 4), max(2, args.warmup // 2), streams)
     value = step_bytes / (ms * 1e-3) / 1e9
     dom = stacks[0]
     dom_ms = time_back_to_back(dom, "fused", max(20, args.steps // 2))
@@ -321,7 +329,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "BASELINE config 1: VGG-16-BN stacks BN->ReLU->MaxPool2x2/2, fp32, "
                                "batch 32, 64x224x224 + 128x112x112 + 256x56x56, indices off",
-                   "rotation_sets": [sb.sets for sb in stacks]},
+                   "rotation_sets": [sb.sets for sb in stacks],
+                   "streams": 1 if args.one_stream else len(stacks)},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "images_per_s": round(dom.images / (ms * 1e-3), 1),
         "speedup_vs_layer_by_layer": None if args.no_baseline else round(ms_lbl / ms, 3),
