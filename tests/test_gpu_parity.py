@@ -338,6 +338,81 @@ def test_run_time_builds(shape, dtype):
         check(layers, x, res, dtype, f"built/{name}{shape}/off", jit=-1)
 
 
+# ------------------------------------------------------------------ random stacks
+def _random_stack(rng, c, h, w, small=False):
+    """A random valid stack: 1..8 layers, every pooling output at least 1 x 1.  `small`: short
+    stacks with windows up to 3 x 3 and strides up to 2 and no residuals -- the shapes the
+    register kernels take when the width is a multiple of the vector width."""
+    layers, res_shapes, n_idx, ew_run = [], [], 0, 0
+    kinds = ["bn", "relu", "leaky", "clamp", "add", "max", "max", "avg", "avg"]
+    if small:
+        kinds.remove("add")
+    for _ in range(int(rng.integers(1, 5 if small else 9))):
+        kind = rng.choice(kinds)
+        if kind in ("max", "avg"):
+            k = (int(rng.integers(1, 4 if small else 6)), int(rng.integers(1, 4 if small else 6)))
+            st = (int(rng.integers(1, 3 if small else 4)), int(rng.integers(1, 3 if small else 4)))
+            p = (int(rng.integers(0, k[0] // 2 + 1)), int(rng.integers(0, k[1] // 2 + 1)))
+            ceil = bool(rng.integers(0, 3) == 0)
+            ho, wo = wl.pool_out(h, k[0], st[0], p[0], ceil), wl.pool_out(w, k[1], st[1], p[1], ceil)
+            if h + 2 * p[0] < k[0] or w + 2 * p[1] < k[1] or ho < 1 or wo < 1:
+                continue
+            if kind == "max":
+                want_idx = bool(rng.integers(0, 2)) and n_idx < 4
+                n_idx += want_idx
+                layers.append(wl.maxpool(k, st, p, want_idx, ceil_mode=ceil))
+            else:
+                layers.append(wl.avgpool(k, st, p, bool(rng.integers(0, 2)), ceil_mode=ceil))
+            h, w, ew_run = ho, wo, 0
+            continue
+        if ew_run >= 5:
+            continue
+        ew_run += 1
+        if kind == "bn":
+            layers.append(wl.bn_params(c, int(rng.integers(0, 1000))))
+        elif kind == "relu":
+            layers.append(wl.relu())
+        elif kind == "leaky":
+            layers.append(wl.leaky_relu(float(rng.choice([0.01, 0.1, 0.3]))))
+        elif kind == "clamp":
+            layers.append(wl.clamp(float(rng.choice([-1.0, 0.0, -0.25])), float(rng.choice([0.5, 1.0, 6.0]))))
+        elif len(res_shapes) < 4:
+            layers.append(wl.add())
+            res_shapes.append((h, w))
+    return layers or [wl.relu()], res_shapes
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_stacks_match_the_oracle(seed):
+    """Seeded random stacks (all layer kinds, odd window shapes, ceil mode, residuals, index
+    outputs) on random small shapes, through the automatic plan and the other plan modes."""
+    rng = np.random.default_rng(1000 + seed)
+    done = 0
+    for case in range(10):
+        n, c = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+        h = int(rng.choice([5, 7, 8, 12, 16, 20, 24, 31, 40]))
+        w = int(rng.choice([5, 8, 9, 12, 16, 24, 32, 40]))
+        small = seed >= 6
+        if small:
+            w = int(rng.choice([8, 16, 24, 32, 40, 48]))
+        dtype = "f32" if (seed + case) % 2 == 0 else "bf16"
+        layers, res_shapes = _random_stack(rng, c, h, w, small)
+        x = wl.activation((n, c, h, w), 2000 + 10 * seed + case, dtype)
+        res = [wl.activation((n, c) + rs, 3000 + i, dtype) for i, rs in enumerate(res_shapes)]
+        opts = [dict(), dict(jit=-1), dict(force_variant=bs.BS_VARIANT_LDS_TILE), dict(breadth_first=1),
+                dict(max_steps_per_sequence=1)][int(rng.integers(0, 5))]
+        label = f"random/{seed}.{case} {[l['kind'] for l in layers]}"
+        try:
+            check(layers, x, res, dtype, label, **opts)
+            done += 1
+        except bs.BrainSlugError as e:
+            # a combination the planner declines (too many element-wise operations on one level,
+            # an index output the tiles cannot cover, ...) is reported, not hidden
+            assert e.status in (4, 6), label
+            print(f"         declined with {e}", flush=True)
+    assert done >= 7
+
+
 # ------------------------------------------------------------------ HIP graph capture
 def test_run_can_be_captured_in_a_hip_graph_and_replayed():
     """bs_stack_run only enqueues kernels on the caller's stream (no allocation, no
