@@ -112,9 +112,34 @@ BS_DEV void unpack(const Raw<BF16, N> &r, float (&v)[N])
     }
 }
 
+// Store N consecutive int32 indices at an address aligned to N * 4 bytes (N = 1, 2, 4; 8 as two
+// halves).  Plain stores: non-temporal ones measured 3..8 % slower here in every kernel.
+template <int N>
+BS_DEV void store_indices(int32_t *p, const int32_t (&v)[N])
+{
+    typedef int i4 __attribute__((ext_vector_type(4)));
+    typedef int i2 __attribute__((ext_vector_type(2)));
+    if constexpr (N == 8) {
+        const i4 a = {v[0], v[1], v[2], v[3]}, b = {v[4], v[5], v[6], v[7]};
+        *reinterpret_cast<i4 *>(p) = a;
+        *reinterpret_cast<i4 *>(p + 4) = b;
+    } else if constexpr (N == 4) {
+        const i4 t = {v[0], v[1], v[2], v[3]};
+        *reinterpret_cast<i4 *>(p) = t;
+    } else if constexpr (N == 2) {
+        const i2 t = {v[0], v[1]};
+        *reinterpret_cast<i2 *>(p) = t;
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) p[i] = v[i];
+    }
+}
+
 // Store N consecutive elements (N * element size is 2, 4, 8 or 16 bytes, naturally aligned).
-// Outputs are written once and not read again by the kernel: vector stores are non-temporal.
-template <bool BF16, int N>
+// Outputs are written once and not read again by the kernel.  NT: non-temporal vector stores,
+// measured 2..7 % faster in every kernel except the two-level sliding-window kernel (7 % slower
+// there), which uses plain stores.
+template <bool BF16, int N, bool NT = true>
 BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
 {
     typedef unsigned u4 __attribute__((ext_vector_type(4)));
@@ -123,10 +148,12 @@ BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
         float *p = static_cast<float *>(base) + elem;
         if constexpr (N == 4) {
             const u4 t = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
-            __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));
+            if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));
+            else *reinterpret_cast<u4 *>(p) = t;
         } else if constexpr (N == 2) {
             const u2 t = {__float_as_uint(v[0]), __float_as_uint(v[1])};
-            __builtin_nontemporal_store(t, reinterpret_cast<u2 *>(p));
+            if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<u2 *>(p));
+            else *reinterpret_cast<u2 *>(p) = t;
         } else {
 #pragma unroll
             for (int i = 0; i < N; ++i) p[i] = v[i];
@@ -140,10 +167,12 @@ BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
                 w[i] = (uint32_t)bf16_bits(v[2 * i]) | ((uint32_t)bf16_bits(v[2 * i + 1]) << 16);
             if constexpr (N == 8) {
                 const u4 t = {w[0], w[1], w[2], w[3]};
-                __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));
+                if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));
+            else *reinterpret_cast<u4 *>(p) = t;
             } else if constexpr (N == 4) {
                 const u2 t = {w[0], w[1]};
-                __builtin_nontemporal_store(t, reinterpret_cast<u2 *>(p));
+                if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<u2 *>(p));
+            else *reinterpret_cast<u2 *>(p) = t;
             } else {
                 *reinterpret_cast<uint32_t *>(p) = w[0];
             }

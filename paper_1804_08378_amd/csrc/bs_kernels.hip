@@ -245,13 +245,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
         if (!valid[u]) continue;
         store_elems<BF16, NO>(k.out, out_off[u], y[u]);
         if (want_idx && is_max) {
-            int32_t *ip = k.idx + out_off[u];
-            if constexpr (NO == 4) *reinterpret_cast<int4 *>(ip) = make_int4(yi[u][0], yi[u][1], yi[u][2], yi[u][3]);
-            else if constexpr (NO == 2) *reinterpret_cast<int2 *>(ip) = make_int2(yi[u][0], yi[u][1]);
-            else {
-#pragma unroll
-                for (int j = 0; j < NO; ++j) ip[j] = yi[u][j];
-            }
+            store_indices<NO>(k.idx + out_off[u], yi[u]);
         }
     }
 }

@@ -281,10 +281,7 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
                 if (vec_store) {
                     store_elems<BF16, VO>(k.out, ooff, y);
                     if constexpr (WANT_IDX) {
-                        if (k.idx) {
-#pragma unroll
-                            for (int e = 0; e < VO; ++e) k.idx[ooff + e] = yi[e];
-                        }
+                        if (k.idx) store_indices<VO>(k.idx + ooff, yi);
                     }
                 } else {
 #pragma unroll
@@ -536,19 +533,16 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
         {
             const uint32_t ooff = oplane + (uint32_t)(oh * k.Wo + ow0);
             if (vec_store) {
-                store_elems<BF16, VO>(k.out, ooff, y);
+                store_elems<BF16, VO, false>(k.out, ooff, y);
                 if constexpr (WANT_IDX) {
-                    if (k.idx) {
-#pragma unroll
-                        for (int e = 0; e < VO; ++e) k.idx[ooff + e] = yi[e];
-                    }
+                    if (k.idx) store_indices<VO>(k.idx + ooff, yi);
                 }
             } else {
 #pragma unroll
                 for (int e = 0; e < VO; ++e)
                     if (ow0 + e < k.Wo) {
                         const float one[1] = {y[e]};
-                        store_elems<BF16, 1>(k.out, ooff + e, one);
+                        store_elems<BF16, 1, false>(k.out, ooff + e, one);
                         if constexpr (WANT_IDX) {
                             if (k.idx) k.idx[ooff + e] = yi[e];
                         }
