@@ -29,8 +29,6 @@ struct Step {
 
 FastDiv make_fastdiv(uint32_t d);
 
-enum KernelId : int32_t { KERNEL_STREAM = 1, KERNEL_POOL_DIRECT = 2, KERNEL_LDS = 3 };
-
 struct Sequence {
     int32_t first_step = 0, n_steps = 0;
     int32_t first_op = 0, n_ops = 0;

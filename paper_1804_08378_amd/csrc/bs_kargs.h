@@ -166,12 +166,6 @@ struct PoolRows2K {
     FastDiv div_cbs, div_chunks, div_c;
 };
 
-// Origin (global row / column of LDS cell 0,0) of every level's region for tile (ti, tj).
-// Used by the kernel and, with the same code, by the planner's bounds audit.
-struct Origins {
-    int32_t r[K_MAX_LEVELS + 1], c[K_MAX_LEVELS + 1];
-};
-
 #if defined(__HIPCC__)
 #define BS_HD __host__ __device__ inline
 #else
@@ -185,9 +179,9 @@ struct Origins {
 #if defined(__HIPCC__)
 __host__ __device__
 #endif
-constexpr int32_t strip_outputs(int32_t sw)
+constexpr int32_t strip_outputs(int32_t /*sw*/)
 {
-    return sw >= 1 ? 4 : 4;
+    return 4;
 }
 
 BS_HD void origin_step(const PoolK &p, int32_t &r0, int32_t &c0)

@@ -1,22 +1,23 @@
 // HIP kernels (gfx950 / CDNA4, wave64) for depth-first execution of a sequence of
 // steps, and their launchers.
 //
-// Three kernel families, following the two code-generation cases of Section 4.1
-// (single-step sequence: values pass from operation to operation directly;
-// multi-step sequence: cached buffer + synchronisation between steps) and the GPU
-// building blocks of Section 4.4 (element-wise; non-stacked pooling; stacked
-// pooling with two on-chip buffers swapped after each step):
+// Kernel families, following the two code-generation cases of Section 4.1 (single-step
+// sequence: values pass from operation to operation directly; multi-step sequence: cached
+// buffer + synchronisation between steps) and the GPU building blocks of Section 4.4
+// (element-wise; non-stacked pooling; stacked pooling with two on-chip buffers swapped
+// after each step).  In this file:
 //
-//   stream_kernel       element-wise only.  128-bit loads/stores, everything in
-//                       registers.
+//   stream_kernel       element-wise only.  128-bit loads/stores, everything in registers.
 //   pool_direct_kernel  one pooling operation with disjoint windows (k == s, p == 0)
 //                       plus element-wise operations before and after it.  Each lane
 //                       owns whole windows: KH 128-bit row loads give VEC/KW outputs.
-//   lds_tile_kernel     any sequence with pooling: a work-group takes a tile of the
-//                       final output, loads the input region it depends on (tile +
-//                       halo) into LDS, and runs step after step between two LDS
-//                       buffers with a barrier in between; halo cells are recomputed
-//                       per tile (Section 5.1 discusses this overlap).
+//   plane_pool_kernel   one pooling operation whose window is the whole (small) plane:
+//                       one lane per plane.
+//
+// In their own files: the register sliding-window kernels for one or two pooling
+// operations with overlapping / padded windows (bs_rows_device.h) and the LDS tile
+// kernels for any sequence (bs_lds_device.h), both also built at plan time for
+// signatures that have no instance compiled into the library (bs_jit.cpp).
 //
 // Arithmetic is float32 with one fixed operation order per layer so that results do
 // not depend on the tiling: BatchNorm is one fused multiply-add with host-folded
