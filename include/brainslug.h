@@ -207,7 +207,7 @@ typedef struct bs_sequence_info {
  * Errors: BS_ERR_NULL, BS_ERR_SHAPE, BS_ERR_PARAM, BS_ERR_UNSUPPORTED, BS_ERR_ALLOC.
  */
 BS_API bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers,
-                                 const int64_t in_shape[4], bs_dtype dtype, bs_stack **out);
+                                 const int64_t in_shape[4], int32_t dtype /* bs_dtype */, bs_stack **out);
 
 /* Free the handle, its host copies and its device parameter table.  NULL is allowed. */
 BS_API void bs_stack_destroy(bs_stack *stack);

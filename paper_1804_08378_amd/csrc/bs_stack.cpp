@@ -46,7 +46,7 @@ using namespace bs;
 extern "C" {
 
 bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers, const int64_t in_shape[4],
-                          bs_dtype dtype, bs_stack **out)
+                          int32_t dtype, bs_stack **out)
 {
     if (!layers || !in_shape || !out) return BS_ERR_NULL;
     if (n_layers < 1 || n_layers > BS_MAX_LAYERS) return BS_ERR_UNSUPPORTED;
