@@ -25,7 +25,7 @@ def run_stack(layers, x, residuals=(), dtype: str = "f32", keep_intermediates: b
     max-pool layer with return_indices, in layer order; `intermediates` is the
     list of every layer's output when requested (else empty).
     """
-    if dtype not in ("f32", "bf16"):
+    if dtype not in ("f32", "bf16", "f16"):
         raise ValueError("dtype")
     cur = np.ascontiguousarray(x, dtype=np.float32)
     res = list(residuals)
@@ -57,8 +57,7 @@ def run_stack(layers, x, residuals=(), dtype: str = "f32", keep_intermediates: b
                             layer.get("count_include_pad", True), layer.get("ceil_mode", False))
         else:
             raise ValueError(f"unknown layer kind {kind!r}")
-        if dtype == "bf16":
-            cur = L.round_bf16(cur)
+        cur = L.round_to(cur, dtype)
         if keep_intermediates:
             inter.append(cur)
     if res:

@@ -52,6 +52,34 @@ BSO_API void bso_round_bf16(float *x, int64_t n)
 }
 
 /* ------------------------------------------------------------------ */
+/* IEEE binary16 rounding: round-to-nearest-even of a float32 to the   */
+/* half-precision format (5 exponent bits, 10 mantissa bits, gradual   */
+/* underflow, overflow to infinity), returned as float32.              */
+/* The grid of representable values around v has spacing               */
+/* 2^(e-10) for |v| in [2^e, 2^(e+1)), e >= -14, and 2^-24 below 2^-14;*/
+/* scaling by that spacing makes the rounding an integer rounding.     */
+/* ------------------------------------------------------------------ */
+static float round_to_f16(float v)
+{
+    if (v != v || v == INFINITY || v == -INFINITY || v == 0.0f) return v;
+    int e;
+    (void)frexpf(v, &e); /* |v| = m * 2^e, m in [0.5, 1) : |v| in [2^(e-1), 2^e) */
+    int ulp_exp = (e - 1) - 10;
+    if (ulp_exp < -24) ulp_exp = -24;           /* subnormal range: fixed spacing */
+    const float scaled = ldexpf(v, -ulp_exp);   /* exact: a power-of-two scaling */
+    const float r = nearbyintf(scaled);         /* ties to even in the default rounding mode */
+    const float y = ldexpf(r, ulp_exp);
+    if (y > 65504.0f) return INFINITY;          /* beyond the largest half value */
+    if (y < -65504.0f) return -INFINITY;
+    return y;
+}
+
+BSO_API void bso_round_f16(float *x, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) x[i] = round_to_f16(x[i]);
+}
+
+/* ------------------------------------------------------------------ */
 /* BatchNorm, inference mode (the "normalization" element-wise layer   */
 /* of Section 2).  Folded form: per channel                            */
 /*     scale = gamma / sqrt(var + eps)                                 */

@@ -136,7 +136,6 @@ def run_stack_tiled(layers, x, residuals=(), dtype="f32", tile=(1, 1)):
                         if not np.array_equal(dst[seen], idx[seen]):
                             raise AssertionError("halo recompute produced a different argmax")
                         dst[...] = idx
-                if dtype == "bf16":
-                    cur = L.round_bf16(cur)
+                cur = L.round_to(cur, dtype)
             out[:, :, rows[0]:rows[1], cols[0]:cols[1]] = cur
     return out, [idx_out[i] for i in sorted(idx_out)]

@@ -27,6 +27,7 @@ def lib():
         path = _build.build(force=False)
         L = C.CDLL(path)
         L.bso_round_bf16.argtypes = [_f32p, _i64]
+        L.bso_round_f16.argtypes = [_f32p, _i64]
         L.bso_bn_fold.argtypes = [_f32p, _f32p, _f32p, _f32p, C.c_double, _i64, _f32p, _f32p]
         L.bso_batchnorm.argtypes = [_f32p, _f32p, _i64, _i64, _i64, _i64, _f32p, _f32p]
         L.bso_batchnorm_textbook_f64.argtypes = [_f32p, _f64p, _i64, _i64, _i64, _i64,
@@ -39,7 +40,7 @@ def lib():
         L.bso_pool_out.restype = _i64
         L.bso_maxpool.argtypes = [_f32p, _f32p, _i32p] + [_i64] * 10 + [C.c_int]
         L.bso_avgpool.argtypes = [_f32p, _f32p] + [_i64] * 10 + [C.c_int, C.c_int]
-        for f in (L.bso_round_bf16, L.bso_bn_fold, L.bso_batchnorm, L.bso_batchnorm_textbook_f64,
+        for f in (L.bso_round_bf16, L.bso_round_f16, L.bso_bn_fold, L.bso_batchnorm, L.bso_batchnorm_textbook_f64,
                   L.bso_relu, L.bso_add, L.bso_maxpool, L.bso_avgpool, L.bso_leaky_relu, L.bso_clamp):
             f.restype = None
         _lib = L
@@ -65,6 +66,21 @@ def round_bf16(x) -> np.ndarray:
     y = _f32(x).copy()
     lib().bso_round_bf16(_p(y), y.size)
     return y
+
+
+def round_f16(x) -> np.ndarray:
+    y = _f32(x).copy()
+    lib().bso_round_f16(_p(y), y.size)
+    return y
+
+
+def round_to(x, dtype: str) -> np.ndarray:
+    """Storage rounding of a layer output: none for "f32", bfloat16 / binary16 otherwise."""
+    if dtype == "bf16":
+        return round_bf16(x)
+    if dtype == "f16":
+        return round_f16(x)
+    return x
 
 
 def bn_fold(gamma, beta, mean, var, eps):

@@ -20,7 +20,7 @@ from __future__ import annotations
 
 import numpy as np
 
-DTYPES = ("f32", "bf16")
+DTYPES = ("f32", "bf16", "f16")
 
 
 def _rng(seed: int) -> np.random.Generator:
@@ -31,8 +31,8 @@ def _rng(seed: int) -> np.random.Generator:
 def activation(shape, seed: int, dtype: str = "f32") -> np.ndarray:
     """N(0,1) activation tensor, float32 storage.
 
-    For dtype "bf16" every value is made representable in bfloat16 (by a
-    round-trip through torch's bfloat16 type), still stored as float32, so the
+    For dtype "bf16" / "f16" every value is made representable in that format (by a
+    round-trip through torch's bfloat16 / numpy's float16 type), still stored as float32, so the
     same array can be handed to the oracle (float32 arrays) and, converted
     losslessly to bfloat16, to the GPU.
     """
@@ -43,6 +43,8 @@ def activation(shape, seed: int, dtype: str = "f32") -> np.ndarray:
         import torch
 
         x = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    elif dtype == "f16":
+        x = x.astype(np.float16).astype(np.float32)
     return x
 
 

@@ -266,6 +266,28 @@ def test_avgpool_sum_order_is_row_major_sequential():
 
 
 # ------------------------------------------------------------ bf16 rounding
+def test_round_f16_vs_library_ties_subnormals_and_overflow():
+    """binary16 rounding against numpy's float16 conversion (an independent implementation):
+    every half value is a fixed point, midpoints between neighbours go to the even one, the
+    subnormal grid has spacing 2^-24, and 65520 is the first value that overflows."""
+    allh = np.arange(65536, dtype=np.uint16).view(np.float16)
+    fin = allh[np.isfinite(allh)].astype(np.float32)
+    assert np.array_equal(L.round_f16(fin).view(np.uint32), fin.view(np.uint32))
+    pos = np.sort(fin[fin >= 0])
+    mid = ((pos[:-1].astype(np.float64) + pos[1:].astype(np.float64)) / 2).astype(np.float32)  # exact in float32
+    for x in (mid, -mid, np.nextafter(mid, np.float32(np.inf)), np.nextafter(mid, np.float32(-np.inf))):
+        assert np.array_equal(L.round_f16(x).view(np.uint32), x.astype(np.float16).astype(np.float32).view(np.uint32))
+    g = np.random.Generator(np.random.Philox(5))
+    r = (g.standard_normal(200000) * np.exp(g.uniform(-20, 12, 200000))).astype(np.float32)
+    with np.errstate(over="ignore"):
+        assert np.array_equal(L.round_f16(r).view(np.uint32), r.astype(np.float16).astype(np.float32).view(np.uint32))
+    sp = np.float32([65504, 65519.996, 65520, 70000, -65520, 2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -25, 2.0 ** -26, 0.0, -0.0])
+    want = np.float32([65504, 65504, np.inf, np.inf, -np.inf, 2.0 ** -24, 0.0, 2.0 ** -24, 0.0, 0.0, -0.0])
+    got = L.round_f16(sp)
+    assert np.array_equal(got, want) and np.signbit(got[-1]) and not np.signbit(got[-2])
+    assert np.isnan(L.round_f16(np.float32([np.nan]))[0])
+
+
 # ------------------------------------------------------------------ further activations
 def test_leaky_relu_closed_forms_and_library():
     x = np.array([-4.0, -1.0, -0.0, 0.0, 0.5, 3.0, -1e-30, np.inf, -np.inf], np.float32).reshape(1, 1, 3, 3)

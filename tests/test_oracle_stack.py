@@ -76,7 +76,7 @@ def _tiny_stacks():
 
 
 @pytest.mark.parametrize("name", list(_tiny_stacks()))
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_depth_first_equals_breadth_first_bit_for_bit(name, dtype):
     """The paper's invariant, for several tile sizes including 1x1 and ragged ones."""
     layers = _tiny_stacks()[name]
@@ -127,7 +127,7 @@ def test_activation_stack_depth_first_equals_breadth_first_and_torch():
     import torch.nn.functional as F
     layers = [wl.leaky_relu(0.1), wl.maxpool(3, 2, 1, True), wl.relu6(), wl.avgpool(2, 2, 0), wl.clamp(-0.25, 0.75)]
     x = wl.activation((2, 3, 12, 16), 10) * 5
-    for dtype in ("f32", "bf16"):
+    for dtype in ("f32", "bf16", "f16"):
         xin = L_round(x, dtype)
         ref, ref_idx, _ = bf.run_stack(layers, xin, (), dtype)
         for tile in ((1, 1), (2, 3), (100, 100)):
@@ -142,7 +142,7 @@ def test_activation_stack_depth_first_equals_breadth_first_and_torch():
 
 def L_round(x, dtype):
     from oracle import layers as L
-    return L.round_bf16(x) if dtype == "bf16" else x
+    return L.round_to(x, dtype)
 
 
 def test_ceil_mode_stack_depth_first_equals_breadth_first_and_torch():
@@ -224,6 +224,25 @@ def test_bf16_stack_rounds_at_every_layer_boundary():
     # float64 -> bf16 vs float32-fma -> bf16 can differ only by double rounding at ties
     assert (out != ref).mean() < 1e-3
     assert np.abs(out - ref).max() <= 1e-2 * np.abs(ref).max()
+
+
+def test_f16_stack_rounds_at_every_layer_boundary_like_the_framework():
+    """binary16 storage: every intermediate is representable in float16, and the stack agrees
+    with the framework's float16 tensors run layer by layer (float32 math inside a layer)."""
+    import torch.nn.functional as F
+    layers = [wl.bn_params(3, 7), wl.relu(), wl.maxpool(3, 2, 1), wl.avgpool(2, 2, 0)]
+    x = wl.activation((2, 3, 12, 16), 8, "f16") * 3
+    x = x.astype(np.float16).astype(np.float32)
+    out, _, inter = bf.run_stack(layers, x, (), "f16", keep_intermediates=True)
+    for t in inter:
+        assert np.array_equal(t, t.astype(np.float16).astype(np.float32))
+    b = layers[0]
+    t = torch.from_numpy(x)
+    t = F.batch_norm(t, *(torch.from_numpy(b[k]) for k in ("mean", "var", "gamma", "beta")), False, 0.0, b["eps"]).half().float()
+    t = F.max_pool2d(F.relu(t), 3, 2, 1)
+    t = F.avg_pool2d(t, 2, 2).half().float().numpy()
+    assert (out != t).mean() < 0.02                       # double-rounding ties of the differently ordered BatchNorm
+    assert np.abs(out - t).max() <= 2e-3 * np.abs(t).max()
 
 
 def test_runner_argument_errors():
