@@ -61,7 +61,9 @@ typedef enum bs_status {
     BS_ERR_JIT = 13         /* a run-time kernel build the caller required has failed      */
 } bs_status;
 
-typedef enum bs_dtype { BS_F32 = 0, BS_BF16 = 1 } bs_dtype;
+/* Storage type of every tensor of a stack; the arithmetic is float32 for all three, each
+ * layer output rounded (nearest-even) to the storage type. */
+typedef enum bs_dtype { BS_F32 = 0, BS_BF16 = 1, BS_F16 = 2 /* IEEE binary16 */ } bs_dtype;
 
 typedef enum bs_layer_kind {
     BS_BATCHNORM = 1, /* inference BatchNorm: y = (x - mean) / sqrt(var + eps) * gamma + beta  */

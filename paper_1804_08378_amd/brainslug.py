@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbrainslug_hip.so")
 
 BS_OK = 0
-BS_F32, BS_BF16 = 0, 1
+BS_F32, BS_BF16, BS_F16 = 0, 1, 2
 BS_BATCHNORM, BS_RELU, BS_ADD, BS_MAXPOOL, BS_AVGPOOL, BS_LEAKY_RELU, BS_CLAMP = 1, 2, 3, 4, 5, 6, 7
 BS_VARIANT_AUTO, BS_VARIANT_STREAM, BS_VARIANT_POOL_DIRECT, BS_VARIANT_LDS_TILE = 0, 1, 2, 3
 BS_VARIANT_POOL_ROWS, BS_VARIANT_PLANE_POOL = 4, 5
@@ -210,7 +210,7 @@ def _marshal_layers(layers, channels):
 
 def bs_stack_create(layers, in_shape, dtype) -> int:
     """Returns the opaque handle (an int).  `dtype` is BS_F32/BS_BF16 or "f32"/"bf16"."""
-    dt = {"f32": BS_F32, "bf16": BS_BF16}.get(dtype, dtype)
+    dt = {"f32": BS_F32, "bf16": BS_BF16, "f16": BS_F16}.get(dtype, dtype)
     arr, keep = _marshal_layers(layers, int(in_shape[1]))
     h = C.c_void_p()
     _check(load().bs_stack_create(arr, len(layers), _shape4(in_shape), int(dt), C.byref(h)),
@@ -352,7 +352,9 @@ class Stack:
 
     def torch_dtype(self):
         import torch
-        return torch.float32 if self.dtype in ("f32", BS_F32) else torch.bfloat16
+        if self.dtype in ("f32", BS_F32):
+            return torch.float32
+        return torch.bfloat16 if self.dtype in ("bf16", BS_BF16) else torch.float16
 
     def alloc_outputs(self, device="cuda", indices=True):
         import torch

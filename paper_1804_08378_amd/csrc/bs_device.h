@@ -23,24 +23,46 @@ BS_DEV uint32_t fdiv(uint32_t n, const FastDiv &f)
     return f.d == 1 ? n : (__umulhi(n, f.mul) >> f.shift);
 }
 
-// ------------------------------------------------------------------ bfloat16
-BS_DEV float bf16_round(float f)
-{
-    // round-to-nearest-even through the compiler's bfloat16 type (v_cvt_pk_bf16_f32)
-    return (float)(__bf16)f;
-}
-BS_DEV uint16_t bf16_bits(float f)
-{
-    __bf16 h = (__bf16)f;
-    return __builtin_bit_cast(uint16_t, h);
-}
-BS_DEV float bf16_up(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+// ------------------------------------------------------- 16-bit storage types
+// DT: 0 = float32, 1 = bfloat16, 2 = IEEE binary16 storage (the values of bs_dtype).  Arithmetic
+// is float32 for all three; a layer's output is rounded to the storage type (nearest-even)
+// by the compiler's conversions (v_cvt_pk_bf16_f32 / v_cvt_f16_f32).
+constexpr int DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2;
 
-template <bool BF16>
+template <int DT>
+BS_DEV uint16_t half_bits(float f)
+{
+    if constexpr (DT == DT_BF16) {
+        const __bf16 h = (__bf16)f;
+        return __builtin_bit_cast(uint16_t, h);
+    } else {
+        const _Float16 h = (_Float16)f;
+        return __builtin_bit_cast(uint16_t, h);
+    }
+}
+
+template <int DT>
+BS_DEV float half_up(uint32_t bits16)
+{
+    if constexpr (DT == DT_BF16) return __uint_as_float(bits16 << 16);
+    else return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+}
+
+template <int DT>
 BS_DEV float round_store(float v)
 {
-    if constexpr (BF16) return bf16_round(v);
-    else return v;
+    if constexpr (DT == DT_BF16) {
+        return (float)(__bf16)v;
+    } else if constexpr (DT == DT_F16) {
+        // A layer's float32 result is rounded to float32 first and to binary16 second.  Without
+        // this barrier the compiler merges a preceding fused multiply-add with the conversion into
+        // one v_fma_mixlo_f16, which rounds once, straight to binary16: a different (if closer)
+        // value in rare double-rounding cases than the layer definition gives.
+        asm("" : "+v"(v));
+        return (float)(_Float16)v;
+    } else {
+        return v;
+    }
 }
 
 // --------------------------------------------------------- vector load/store
@@ -56,21 +78,21 @@ struct RawT<4> { using type = uint32_t; };
 template <>
 struct RawT<2> { using type = uint16_t; };
 
-template <bool BF16, int N>
+template <int DT, int N>
 struct Raw {
-    using type = typename RawT<N * (BF16 ? 2 : 4)>::type;
+    using type = typename RawT<N * (DT != DT_F32 ? 2 : 4)>::type;
     type q;
 };
 
 // NT: non-temporal (streaming) load for data that is read exactly once; leave it off where
 // neighbouring lanes or tiles re-read the same cache lines.
-template <bool BF16, int N, bool NT = false>
-BS_DEV Raw<BF16, N> load_raw(const void *base, uint32_t elem)
+template <int DT, int N, bool NT = false>
+BS_DEV Raw<DT, N> load_raw(const void *base, uint32_t elem)
 {
-    using T = typename Raw<BF16, N>::type;
-    Raw<BF16, N> r;
-    const char *ptr = static_cast<const char *>(base) + (size_t)elem * (BF16 ? 2 : 4);
-    constexpr int BYTES = N * (BF16 ? 2 : 4);
+    using T = typename Raw<DT, N>::type;
+    Raw<DT, N> r;
+    const char *ptr = static_cast<const char *>(base) + (size_t)elem * (DT != DT_F32 ? 2 : 4);
+    constexpr int BYTES = N * (DT != DT_F32 ? 2 : 4);
     if constexpr (!NT) {
         r.q = *reinterpret_cast<const T *>(ptr);
     } else if constexpr (BYTES == 16) {
@@ -87,26 +109,31 @@ BS_DEV Raw<BF16, N> load_raw(const void *base, uint32_t elem)
     return r;
 }
 
-template <bool BF16, int N>
-BS_DEV void unpack(const Raw<BF16, N> &r, float (&v)[N])
+template <int DT, int N>
+BS_DEV void unpack(const Raw<DT, N> &r, float (&v)[N])
 {
-    constexpr int BYTES = N * (BF16 ? 2 : 4);
+    constexpr int BYTES = N * (DT != DT_F32 ? 2 : 4);
     if constexpr (BYTES == 2) {
-        v[0] = __uint_as_float((uint32_t)r.q << 16);
+        v[0] = half_up<DT>(r.q);
     } else {
         constexpr int WORDS = BYTES / 4;
         uint32_t w[WORDS];
         if constexpr (BYTES == 16) { w[0] = r.q.x; w[1] = r.q.y; w[2] = r.q.z; w[3] = r.q.w; }
         else if constexpr (BYTES == 8) { w[0] = r.q.x; w[1] = r.q.y; }
         else w[0] = r.q;
-        if constexpr (!BF16) {
+        if constexpr (DT == DT_F32) {
 #pragma unroll
             for (int i = 0; i < WORDS; ++i) v[i] = __uint_as_float(w[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < WORDS; ++i) {
-                v[2 * i] = __uint_as_float(w[i] << 16);
-                v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+                if constexpr (DT == DT_BF16) {
+                    v[2 * i] = __uint_as_float(w[i] << 16);
+                    v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+                } else {
+                    v[2 * i] = half_up<DT>(w[i] & 0xffffu);
+                    v[2 * i + 1] = half_up<DT>(w[i] >> 16);
+                }
             }
         }
     }
@@ -139,12 +166,12 @@ BS_DEV void store_indices(int32_t *p, const int32_t (&v)[N])
 // Outputs are written once and not read again by the kernel.  NT: non-temporal vector stores,
 // measured 2..7 % faster in every kernel except the two-level sliding-window kernel (7 % slower
 // there), which uses plain stores.
-template <bool BF16, int N, bool NT = true>
+template <int DT, int N, bool NT = true>
 BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
 {
     typedef unsigned u4 __attribute__((ext_vector_type(4)));
     typedef unsigned u2 __attribute__((ext_vector_type(2)));
-    if constexpr (!BF16) {
+    if constexpr (DT == DT_F32) {
         float *p = static_cast<float *>(base) + elem;
         if constexpr (N == 4) {
             const u4 t = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
@@ -164,7 +191,7 @@ BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
             uint32_t w[N / 2];
 #pragma unroll
             for (int i = 0; i < N / 2; ++i)
-                w[i] = (uint32_t)bf16_bits(v[2 * i]) | ((uint32_t)bf16_bits(v[2 * i + 1]) << 16);
+                w[i] = (uint32_t)half_bits<DT>(v[2 * i]) | ((uint32_t)half_bits<DT>(v[2 * i + 1]) << 16);
             if constexpr (N == 8) {
                 const u4 t = {w[0], w[1], w[2], w[3]};
                 if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));
@@ -178,7 +205,7 @@ BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < N; ++i) p[i] = bf16_bits(v[i]);
+            for (int i = 0; i < N; ++i) p[i] = half_bits<DT>(v[i]);
         }
     }
 }

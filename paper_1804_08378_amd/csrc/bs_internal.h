@@ -98,6 +98,9 @@ struct bs_stack {
 namespace bs {
 
 size_t dtype_size(int32_t dtype);
+// The signature tables of the sliding-window and tile kernels are compiled into the library
+// for float32 and bfloat16; binary16 stacks get those kernels as run-time builds.
+inline bool dtype_has_tables(int32_t dtype) { return dtype == BS_F32 || dtype == BS_BF16; }
 
 // planner (host only)
 bs_status build_operations(bs_stack *s);
@@ -115,19 +118,19 @@ void set_hip_error(int32_t e);
 // kernel template can be instantiated for it at run time; *_expr = that instance's name
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);
 bool rows_buildable(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post, int32_t vec);
-std::string rows_expr(const PoolRowsK &k, bool bf16, bool want_idx);
-bs_status launch_rows(const PoolRowsK &k, bool bf16, int64_t grid, int32_t threads, void *stream);
+std::string rows_expr(const PoolRowsK &k, int32_t dtype, bool want_idx);
+bs_status launch_rows(const PoolRowsK &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
 // bs_rows2.hip
 bool rows2_supported(const PoolRows2K &k);
 bool rows2_buildable(const PoolRows2K &k, int32_t vec);
-std::string rows2_expr(const PoolRows2K &k, bool bf16, bool want_idx);
-bs_status launch_rows2(const PoolRows2K &k, bool bf16, int64_t grid, int32_t threads, void *stream);
+std::string rows2_expr(const PoolRows2K &k, int32_t dtype, bool want_idx);
+bs_status launch_rows2(const PoolRows2K &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
 bool lds_fast_path(const LdsSeqK &k);
-bool lds_precompiled(const LdsSeqK &k, bool bf16);
+bool lds_precompiled(const LdsSeqK &k, int32_t dtype);
 bool lds_buildable(const LdsSeqK &k);
-std::string lds_expr(const LdsSeqK &k, bool bf16, bool want_idx);
-bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
+std::string lds_expr(const LdsSeqK &k, int32_t dtype, bool want_idx);
+bs_status launch_lds(const LdsSeqK &k, int32_t dtype, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
 // bs_jit.cpp
 bool jit_enabled();
 std::string jit_last_log();

@@ -37,7 +37,7 @@ namespace bs {
 // no load here is predicated.
 //   c[u]    channel of vector u (BatchNorm parameters)
 //   off[u]  element offset of vector u in this level's tensors (residual loads)
-template <bool BF16, int VEC, int U>
+template <int DT, int VEC, int U>
 BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (&off)[U],
                      const EwOp *ew, int32_t n_ew, const float *__restrict__ params, int32_t C,
                      const void *const *res)
@@ -55,7 +55,7 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<BF16>(__builtin_fmaf(x[u][i], sc[u], sh[u]));
+                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(__builtin_fmaf(x[u][i], sc[u], sh[u]));
         } else if (kind == OP_RELU) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -66,25 +66,25 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<BF16>(x[u][i] > 0.0f ? x[u][i] : x[u][i] * slope);
+                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(x[u][i] > 0.0f ? x[u][i] : x[u][i] * slope);
         } else if (kind == OP_CLAMP) {
             const float lo = params[arg], hi = params[arg + 1];
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i)  // v_max / v_min: a NaN becomes lo
-                    x[u][i] = round_store<BF16>(__builtin_fminf(__builtin_fmaxf(x[u][i], lo), hi));
+                    x[u][i] = round_store<DT>(__builtin_fminf(__builtin_fmaxf(x[u][i], lo), hi));
         } else {  // OP_ADD
             const void *rp = res[arg];
-            Raw<BF16, VEC> rr[U];
+            Raw<DT, VEC> rr[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) rr[u] = load_raw<BF16, VEC, true>(rp, off[u]);
+            for (int u = 0; u < U; ++u) rr[u] = load_raw<DT, VEC, true>(rp, off[u]);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float r[VEC];
-                unpack<BF16, VEC>(rr[u], r);
+                unpack<DT, VEC>(rr[u], r);
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<BF16>(x[u][i] + r[i]);
+                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(x[u][i] + r[i]);
             }
         }
     }
@@ -94,12 +94,12 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
 // stream_kernel: element-wise only sequence.  A work-group takes nthr * U
 // consecutive 128-bit vectors; lane t handles vectors t, t + nthr, ...
 // =============================================================================
-template <bool BF16, int VEC, int U>
+template <int DT, int VEC, int U>
 __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
 {
     const uint32_t nthr = blockDim.x;
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
-    Raw<BF16, VEC> raw[U];
+    Raw<DT, VEC> raw[U];
     bool valid[U];
     uint32_t off[U];
     int32_t c[U];
@@ -109,17 +109,17 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
         valid[u] = i < k.total;
         i = valid[u] ? i : 0u;
         off[u] = i * VEC;
-        raw[u] = load_raw<BF16, VEC, true>(k.in, off[u]);
+        raw[u] = load_raw<DT, VEC, true>(k.in, off[u]);
         const uint32_t plane = fdiv(i, k.div_plane);
         c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
     }
     float x[U][VEC];
 #pragma unroll
-    for (int u = 0; u < U; ++u) unpack<BF16, VEC>(raw[u], x[u]);
-    apply_ew<BF16, VEC, U>(x, c, off, k.ew, k.n_ew, k.params, k.C, k.res);
+    for (int u = 0; u < U; ++u) unpack<DT, VEC>(raw[u], x[u]);
+    apply_ew<DT, VEC, U>(x, c, off, k.ew, k.n_ew, k.params, k.C, k.res);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (valid[u]) store_elems<BF16, VEC>(k.out, off[u], x[u]);
+        if (valid[u]) store_elems<DT, VEC>(k.out, off[u], x[u]);
 }
 
 // =============================================================================
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
 // run time; 1 is compiled for "BatchNorm, ReLU, pool" with nothing after the pool (the
 // VGG stack, the DenseNet transition), whose BatchNorm parameters are requested together
 // with the data so a wave makes one round trip to memory instead of two.
-template <bool BF16, int VEC, int KH, int KW, int U, int SIG>
+template <int DT, int VEC, int KH, int KW, int U, int SIG>
 __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 {
     constexpr int NO = VEC / KW;  // outputs per unit
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
     const uint32_t wv = k.div_wv.d;
 
-    Raw<BF16, VEC> raw[U][KH];
+    Raw<DT, VEC> raw[U][KH];
     bool valid[U];
     uint32_t in_off[U], out_off[U], idx0[U];
     int32_t c[U];
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
         in_off[u] = plane * (uint32_t)(k.H * k.W) + idx0[u];
         out_off[u] = (plane * (uint32_t)k.Ho + oh) * (uint32_t)k.Wo + cv * NO;
 #pragma unroll
-        for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<BF16, VEC, true>(k.in, in_off[u] + dh * (uint32_t)k.W);
+        for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<DT, VEC, true>(k.in, in_off[u] + dh * (uint32_t)k.W);
     }
     float sc[U], sh[U];
     if constexpr (SIG == 1) {
@@ -184,16 +184,16 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
         for (int dh = 0; dh < KH; ++dh) {
             c1[dh] = c[u];
             o1[dh] = in_off[u] + dh * (uint32_t)k.W;
-            unpack<BF16, VEC>(raw[u][dh], x[dh]);
+            unpack<DT, VEC>(raw[u][dh], x[dh]);
         }
         if constexpr (SIG == 1) {
 #pragma unroll
             for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i)
-                    x[dh][i] = __builtin_fmaxf(round_store<BF16>(__builtin_fmaf(x[dh][i], sc[u], sh[u])), 0.0f);
+                    x[dh][i] = __builtin_fmaxf(round_store<DT>(__builtin_fmaf(x[dh][i], sc[u], sh[u])), 0.0f);
         } else {
-            apply_ew<BF16, VEC, KH>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
+            apply_ew<DT, VEC, KH>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
         }
         if (is_max) {
             if (want_idx) {
@@ -235,16 +235,16 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
                 for (int dh = 0; dh < KH; ++dh)
 #pragma unroll
                     for (int dw = 0; dw < KW; ++dw) sum = sum + x[dh][j * KW + dw];
-                y[u][j] = round_store<BF16>(sum * k.pool.inv_kk);
+                y[u][j] = round_store<DT>(sum * k.pool.inv_kk);
                 yi[u][j] = 0;
             }
         }
     }
-    if constexpr (SIG == 0) apply_ew<BF16, NO, U>(y, c, out_off, k.post, k.n_post, k.params, k.C, k.res);
+    if constexpr (SIG == 0) apply_ew<DT, NO, U>(y, c, out_off, k.post, k.n_post, k.params, k.C, k.res);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (!valid[u]) continue;
-        store_elems<BF16, NO>(k.out, out_off[u], y[u]);
+        store_elems<DT, NO>(k.out, out_off[u], y[u]);
         if (want_idx && is_max) {
             store_indices<NO>(k.idx + out_off[u], yi[u]);
         }
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 // elements requested at a time; planes are small here (the planner sends large ones to the
 // tile kernels).  A plane is contiguous, so a lane's loads fall into a few cache lines.
 // =============================================================================
-template <bool BF16>
+template <int DT>
 __global__ __launch_bounds__(256) void plane_pool_kernel(const PoolDirectK k)
 {
     constexpr int U = 8;
@@ -271,15 +271,15 @@ __global__ __launch_bounds__(256) void plane_pool_kernel(const PoolDirectK k)
     float acc = is_max ? -INFINITY : 0.0f;
     int32_t bi = 0;  // first cell of the plane
     for (uint32_t i0 = 0; i0 < hw; i0 += U) {
-        Raw<BF16, 1> raw[U];
+        Raw<DT, 1> raw[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) raw[u] = load_raw<BF16, 1>(k.in, base + min(i0 + u, hw - 1));
+        for (int u = 0; u < U; ++u) raw[u] = load_raw<DT, 1>(k.in, base + min(i0 + u, hw - 1));
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float x[1][1];
-            unpack<BF16, 1>(raw[u], x[0]);
+            unpack<DT, 1>(raw[u], x[0]);
             const uint32_t o1[1] = {base + min(i0 + u, hw - 1)};
-            apply_ew<BF16, 1, 1>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
+            apply_ew<DT, 1, 1>(x, c1, o1, k.pre, k.n_pre, k.params, k.C, k.res);
             const float v = x[0][0];
             if (i0 + u < hw) {
                 if (is_max) {
@@ -292,11 +292,11 @@ __global__ __launch_bounds__(256) void plane_pool_kernel(const PoolDirectK k)
             }
         }
     }
-    float y[1][1] = {{is_max ? acc : round_store<BF16>(acc * k.pool.inv_kk)}};
+    float y[1][1] = {{is_max ? acc : round_store<DT>(acc * k.pool.inv_kk)}};
     const uint32_t oo[1] = {plane};  // Ho = Wo = 1: the output (and a residual of its shape) is indexed by plane
-    apply_ew<BF16, 1, 1>(y, c1, oo, k.post, k.n_post, k.params, k.C, k.res);
+    apply_ew<DT, 1, 1>(y, c1, oo, k.post, k.n_post, k.params, k.C, k.res);
     if (live) {
-        store_elems<BF16, 1>(k.out, plane, y[0]);
+        store_elems<DT, 1>(k.out, plane, y[0]);
         if (k.idx && is_max) k.idx[plane] = bi;
     }
 }
@@ -354,29 +354,29 @@ void free_params(bs_stack *s)
     }
 }
 
-template <bool BF16, int VEC, int KH>
+template <int DT, int VEC, int KH>
 static void launch_direct_kw(const PoolDirectK &k, int kw, dim3 grid, dim3 block, hipStream_t st)
 {
     if constexpr (VEC == 8) {
-        if (kw == 8) { pool_direct_kernel<BF16, VEC, KH, 8, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k); return; }
+        if (kw == 8) { pool_direct_kernel<DT, VEC, KH, 8, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k); return; }
     }
     if constexpr (KH == 2) {
         const bool bn_relu_pool = k.n_pre == 2 && k.pre[0].kind == OP_BN && k.pre[1].kind == OP_RELU && k.n_post == 0;
-        if (kw == 2 && bn_relu_pool) { pool_direct_kernel<BF16, VEC, 2, 2, K_DIRECT_U, 1><<<grid, block, 0, st>>>(k); return; }
+        if (kw == 2 && bn_relu_pool) { pool_direct_kernel<DT, VEC, 2, 2, K_DIRECT_U, 1><<<grid, block, 0, st>>>(k); return; }
     }
-    if (kw == 1) pool_direct_kernel<BF16, VEC, KH, 1, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
-    else if (kw == 2) pool_direct_kernel<BF16, VEC, KH, 2, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
-    else pool_direct_kernel<BF16, VEC, KH, 4, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
+    if (kw == 1) pool_direct_kernel<DT, VEC, KH, 1, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
+    else if (kw == 2) pool_direct_kernel<DT, VEC, KH, 2, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
+    else pool_direct_kernel<DT, VEC, KH, 4, K_DIRECT_U, 0><<<grid, block, 0, st>>>(k);
 }
 
-template <bool BF16, int VEC>
+template <int DT, int VEC>
 static void launch_direct(const PoolDirectK &k, dim3 grid, dim3 block, hipStream_t st)
 {
     switch (k.pool.kh) {
-    case 1: launch_direct_kw<BF16, VEC, 1>(k, k.pool.kw, grid, block, st); break;
-    case 2: launch_direct_kw<BF16, VEC, 2>(k, k.pool.kw, grid, block, st); break;
-    case 3: launch_direct_kw<BF16, VEC, 3>(k, k.pool.kw, grid, block, st); break;
-    default: launch_direct_kw<BF16, VEC, 4>(k, k.pool.kw, grid, block, st); break;
+    case 1: launch_direct_kw<DT, VEC, 1>(k, k.pool.kw, grid, block, st); break;
+    case 2: launch_direct_kw<DT, VEC, 2>(k, k.pool.kw, grid, block, st); break;
+    case 3: launch_direct_kw<DT, VEC, 3>(k, k.pool.kw, grid, block, st); break;
+    default: launch_direct_kw<DT, VEC, 4>(k, k.pool.kw, grid, block, st); break;
     }
 }
 
@@ -392,7 +392,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
                           const void *const *res, int32_t *const *idx, void *stream)
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool bf16 = s->dtype == BS_BF16;
+    const int32_t dtype = s->dtype;
     if (q.grid < 1 || q.grid > 0x7fffffffll) return BS_ERR_UNSUPPORTED;
     const dim3 grid((uint32_t)q.grid), block((uint32_t)q.threads);
     const void *rp[K_MAX_RES] = {nullptr, nullptr, nullptr, nullptr};
@@ -405,12 +405,15 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         StreamK k = q.stream;
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
-        if (bf16) {
-            if (q.vec == 8) stream_kernel<true, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
-            else stream_kernel<true, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
+        if (dtype == BS_BF16) {
+            if (q.vec == 8) stream_kernel<DT_BF16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            else stream_kernel<DT_BF16, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
+        } else if (dtype == BS_F16) {
+            if (q.vec == 8) stream_kernel<DT_F16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            else stream_kernel<DT_F16, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
         } else {
-            if (q.vec == 4) stream_kernel<false, 4, K_STREAM_U><<<grid, block, 0, st>>>(k);
-            else stream_kernel<false, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            if (q.vec == 4) stream_kernel<DT_F32, 4, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            else stream_kernel<DT_F32, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
         }
         break;
     }
@@ -419,8 +422,9 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];
-        if (bf16) launch_direct<true, 8>(k, grid, block, st);
-        else launch_direct<false, 4>(k, grid, block, st);
+        if (dtype == BS_BF16) launch_direct<DT_BF16, 8>(k, grid, block, st);
+        else if (dtype == BS_F16) launch_direct<DT_F16, 8>(k, grid, block, st);
+        else launch_direct<DT_F32, 4>(k, grid, block, st);
         break;
     }
     case BS_VARIANT_PLANE_POOL: {
@@ -428,8 +432,9 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];
-        if (bf16) plane_pool_kernel<true><<<grid, block, 0, st>>>(k);
-        else plane_pool_kernel<false><<<grid, block, 0, st>>>(k);
+        if (dtype == BS_BF16) plane_pool_kernel<DT_BF16><<<grid, block, 0, st>>>(k);
+        else if (dtype == BS_F16) plane_pool_kernel<DT_F16><<<grid, block, 0, st>>>(k);
+        else plane_pool_kernel<DT_F32><<<grid, block, 0, st>>>(k);
         break;
     }
     case BS_VARIANT_POOL_ROWS: {
@@ -439,7 +444,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
             k.idx = ip[0];
             const bool want_idx = k.idx != nullptr && k.pool2.kind == OP_MAXPOOL;
             const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
-                                       : launch_rows2(k, bf16, q.grid, q.threads, stream);
+                                       : launch_rows2(k, dtype, q.grid, q.threads, stream);
             if (ls != BS_OK) return ls;
             break;
         }
@@ -448,7 +453,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.idx = ip[0];
         const bool want_idx = k.idx != nullptr && k.pool.kind == OP_MAXPOOL;
         const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
-                                   : launch_rows(k, bf16, q.grid, q.threads, stream);
+                                   : launch_rows(k, dtype, q.grid, q.threads, stream);
         if (ls != BS_OK) return ls;
         break;
     }
@@ -460,7 +465,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         bool want_idx = false;
         for (int j = 0; j < q.n_idx; ++j) want_idx = want_idx || ip[j] != nullptr;
         const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
-                                   : launch_lds(k, bf16, q.grid, q.threads, q.lds_bytes, stream);
+                                   : launch_lds(k, dtype, q.grid, q.threads, q.lds_bytes, stream);
         if (ls != BS_OK) return ls;
         break;
     }

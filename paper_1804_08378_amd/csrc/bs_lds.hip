@@ -39,7 +39,7 @@ static bool pool_is(const PoolK &q)
 
 enum { LAUNCH = 0, DRY_SIGNATURE = 1, DRY_FULL = 2 };  // what the table walk does on a match
 
-template <bool BF16, int VEC, int EW0, class... Ls>
+template <int DT, int VEC, int EW0, class... Ls>
 static bool try_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st, int dry)
 {
     constexpr int NL = (int)sizeof...(Ls);
@@ -51,40 +51,40 @@ static bool try_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size
     if (dry == DRY_SIGNATURE) return true;
     if (k.delta0 != sig_delta0<VEC, Ls...>()) return false;
     if (dry == DRY_FULL) return true;
-    if (want_idx) lds_sig_kernel<BF16, VEC, true, EW0, Ls...><<<grid, block, lds, st>>>(k);
-    else lds_sig_kernel<BF16, VEC, false, EW0, Ls...><<<grid, block, lds, st>>>(k);
+    if (want_idx) lds_sig_kernel<DT, VEC, true, EW0, Ls...><<<grid, block, lds, st>>>(k);
+    else lds_sig_kernel<DT, VEC, false, EW0, Ls...><<<grid, block, lds, st>>>(k);
     return true;
 }
 
-template <bool BF16, int VEC, int EW0, class LV>
+template <int DT, int VEC, int EW0, class LV>
 static bool try_rep(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st, int dry)
 {
     if (k.n_levels < 3 || (dry != DRY_SIGNATURE && k.vec != VEC) || ew_code(k.level[0]) != EW0) return false;
     for (int l = 1; l <= k.n_levels; ++l)
         if (!pool_is<typename LV::P>(k.pool[l]) || ew_code(k.level[l]) != LV::EW::code) return false;
     if (dry != LAUNCH) return true;
-    if (want_idx) lds_rep_kernel<BF16, VEC, true, EW0, LV><<<grid, block, lds, st>>>(k);
-    else lds_rep_kernel<BF16, VEC, false, EW0, LV><<<grid, block, lds, st>>>(k);
+    if (want_idx) lds_rep_kernel<DT, VEC, true, EW0, LV><<<grid, block, lds, st>>>(k);
+    else lds_rep_kernel<DT, VEC, false, EW0, LV><<<grid, block, lds, st>>>(k);
     return true;
 }
 
 // Stack signatures with a dedicated build.  First match wins; anything else runs the
 // run-time build.
-template <bool BF16, int VEC>
+template <int DT, int VEC>
 static bool launch_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, size_t lds, hipStream_t st, int dry)
 {
     // BN -> ReLU -> MaxPool 3/2/1 (ResNet stem), and the pool on its own (layer by layer)
-    if (try_sig<BF16, VEC, EW_BN_RELU, Lvl<Max3s2p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s2p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<DT, VEC, EW_BN_RELU, Lvl<Max3s2p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<DT, VEC, EW_NONE, Lvl<Max3s2p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
     // BN -> ReLU -> AvgPool 3/1/1 -> MaxPool 3/2/1 -> BN -> ReLU (halo stress), and its average alone
-    if (try_sig<BF16, VEC, EW_BN_RELU, Lvl<Avg3s1p1, EW_NONE>, Lvl<Max3s2p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Avg3s1p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<DT, VEC, EW_BN_RELU, Lvl<Avg3s1p1, EW_NONE>, Lvl<Max3s2p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<DT, VEC, EW_NONE, Lvl<Avg3s1p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
     // <MaxPool 3/1/1, BN, ReLU> blocks of Section 5.1: one and two per sequence, and the pool alone
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
-    if (try_sig<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<DT, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<DT, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_sig<DT, VEC, EW_NONE, Lvl<Max3s1p1, EW_NONE>>(k, want_idx, grid, block, lds, st, dry)) return true;
     // three or more of those blocks in one sequence
-    if (try_rep<BF16, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
+    if (try_rep<DT, VEC, EW_NONE, Lvl<Max3s1p1, EW_BN_RELU>>(k, want_idx, grid, block, lds, st, dry)) return true;
     return false;
 }
 
@@ -93,15 +93,16 @@ static bool launch_sig(const LdsSeqK &k, bool want_idx, dim3 grid, dim3 block, s
 // merging steps into a sequence that would fall back to the much slower run-time build.
 bool lds_fast_path(const LdsSeqK &k)
 {
-    return launch_sig<false, 4>(k, false, dim3(1), dim3(64), 0, nullptr, DRY_SIGNATURE);
+    return launch_sig<DT_F32, 4>(k, false, dim3(1), dim3(64), 0, nullptr, DRY_SIGNATURE);
 }
 
 // Will launch_lds run a pre-compiled signature / repeated build for this planned sequence
 // (signature, vector width and row alignment all match)?
-bool lds_precompiled(const LdsSeqK &k, bool bf16)
+bool lds_precompiled(const LdsSeqK &k, int32_t dtype)
 {
-    return bf16 ? launch_sig<true, 8>(k, false, dim3(1), dim3(64), 0, nullptr, DRY_FULL)
-                : launch_sig<false, 4>(k, false, dim3(1), dim3(64), 0, nullptr, DRY_FULL);
+    if (!dtype_has_tables(dtype)) return false;
+    return dtype == BS_BF16 ? launch_sig<DT_BF16, 8>(k, false, dim3(1), dim3(64), 0, nullptr, DRY_FULL)
+                            : launch_sig<DT_F32, 4>(k, false, dim3(1), dim3(64), 0, nullptr, DRY_FULL);
 }
 
 // Can lds_sig_kernel be instantiated for this planned sequence?  Its level-1 phase takes the
@@ -115,10 +116,10 @@ bool lds_buildable(const LdsSeqK &k)
 }
 
 // Name of the lds_sig_kernel instance for this sequence (run-time build).
-std::string lds_expr(const LdsSeqK &k, bool bf16, bool want_idx)
+std::string lds_expr(const LdsSeqK &k, int32_t dtype, bool want_idx)
 {
     char b[200];
-    std::snprintf(b, sizeof b, "bs::lds_sig_kernel<%s, %d, %s, %d", bf16 ? "true" : "false", k.vec,
+    std::snprintf(b, sizeof b, "bs::lds_sig_kernel<%d, %d, %s, %d", dtype, k.vec,
                   want_idx ? "true" : "false", ew_code(k.level[0]));
     std::string e = b;
     for (int l = 1; l <= k.n_levels; ++l) {
@@ -130,7 +131,7 @@ std::string lds_expr(const LdsSeqK &k, bool bf16, bool want_idx)
     return e + ">";
 }
 
-bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid_n, int32_t threads, uint64_t lds_bytes, void *stream)
+bs_status launch_lds(const LdsSeqK &k, int32_t dtype, int64_t grid_n, int32_t threads, uint64_t lds_bytes, void *stream)
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
@@ -138,17 +139,22 @@ bs_status launch_lds(const LdsSeqK &k, bool bf16, int64_t grid_n, int32_t thread
     bool want_idx = false;
     for (int l = 1; l <= k.n_levels; ++l)
         if (k.pool[l].idx_slot >= 0 && k.idx[k.pool[l].idx_slot]) want_idx = true;
-    if (bf16) {
+    if (dtype == BS_F16) {  // no signature table for binary16: the run-time-shape kernel
+        if (k.vec == 8) lds_tile_kernel<DT_F16, 8><<<grid, block, lds, st>>>(k);
+        else lds_tile_kernel<DT_F16, 1><<<grid, block, lds, st>>>(k);
+    } else if (dtype == BS_BF16) {
         if (k.vec == 8) {
-            if (!launch_sig<true, 8>(k, want_idx, grid, block, lds, st, LAUNCH)) lds_tile_kernel<true, 8><<<grid, block, lds, st>>>(k);
+            if (!launch_sig<DT_BF16, 8>(k, want_idx, grid, block, lds, st, LAUNCH))
+                lds_tile_kernel<DT_BF16, 8><<<grid, block, lds, st>>>(k);
         } else {
-            lds_tile_kernel<true, 1><<<grid, block, lds, st>>>(k);
+            lds_tile_kernel<DT_BF16, 1><<<grid, block, lds, st>>>(k);
         }
     } else {
         if (k.vec == 4) {
-            if (!launch_sig<false, 4>(k, want_idx, grid, block, lds, st, LAUNCH)) lds_tile_kernel<false, 4><<<grid, block, lds, st>>>(k);
+            if (!launch_sig<DT_F32, 4>(k, want_idx, grid, block, lds, st, LAUNCH))
+                lds_tile_kernel<DT_F32, 4><<<grid, block, lds, st>>>(k);
         } else {
-            lds_tile_kernel<false, 1><<<grid, block, lds, st>>>(k);
+            lds_tile_kernel<DT_F32, 1><<<grid, block, lds, st>>>(k);
         }
     }
     return BS_OK;

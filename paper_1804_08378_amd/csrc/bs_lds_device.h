@@ -126,7 +126,7 @@ BS_DEV void load_ew_regs(const LevelK &lv, const float *params, int32_t C, int32
 
 // Element-wise operations of a level on N values of one plane.  CONTIG: the N values are
 // consecutive elements starting at off[0] (one vector residual load); else off[i] each.
-template <bool BF16, int N, bool CONTIG, class EW>
+template <int DT, int N, bool CONTIG, class EW>
 BS_DEV void apply_level_ew(float (&x)[N], const LevelK &lv, const EwRegs<EW> &er, const void *const *res,
                            const uint32_t (&off)[CONTIG ? 1 : N])
 {
@@ -136,34 +136,34 @@ BS_DEV void apply_level_ew(float (&x)[N], const LevelK &lv, const EwRegs<EW> &er
         const int32_t kind = EW::kind(lv, j);
         if (kind == OP_BN) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fmaf(x[i], er.sc[j], er.sh[j]));
+            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(__builtin_fmaf(x[i], er.sc[j], er.sh[j]));
         } else if (kind == OP_RELU) {
             // v_max_f32: NaN -> 0, and max(-0, +0) = +0 in either operand order
 #pragma unroll
             for (int i = 0; i < N; ++i) x[i] = __builtin_fmaxf(x[i], 0.0f);
         } else if (kind == OP_LEAKY) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(x[i] > 0.0f ? x[i] : x[i] * er.sc[j]);
+            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(x[i] > 0.0f ? x[i] : x[i] * er.sc[j]);
         } else if (kind == OP_CLAMP) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fminf(__builtin_fmaxf(x[i], er.sc[j]), er.sh[j]));
+            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(__builtin_fminf(__builtin_fmaxf(x[i], er.sc[j]), er.sh[j]));
         } else {
             const void *rp = res[lv.ew[j].arg];
             float r[N];
             if constexpr (CONTIG) {
-                const Raw<BF16, N> rr = load_raw<BF16, N>(rp, off[0]);
-                unpack<BF16, N>(rr, r);
+                const Raw<DT, N> rr = load_raw<DT, N>(rp, off[0]);
+                unpack<DT, N>(rr, r);
             } else {
 #pragma unroll
                 for (int i = 0; i < N; ++i) {
-                    const Raw<BF16, 1> rr = load_raw<BF16, 1>(rp, off[i]);
+                    const Raw<DT, 1> rr = load_raw<DT, 1>(rp, off[i]);
                     float one[1];
-                    unpack<BF16, 1>(rr, one);
+                    unpack<DT, 1>(rr, one);
                     r[i] = one[0];
                 }
             }
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(x[i] + r[i]);
+            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(x[i] + r[i]);
         }
     }
 }
@@ -399,7 +399,7 @@ BS_DEV TileCtx tile_ctx(const LdsSeqK &k)
 
 // ---------------- phase 0: load the level-0 rectangle, apply its element-wise ops ----
 // (r0, c0): global row / column of the rectangle's origin; padv: padding of pooling op 1.
-template <bool BF16, int VEC, class EW>
+template <int DT, int VEC, class EW>
 BS_DEV void phase0(const LdsSeqK &k, const TileCtx &t, float *lds, int32_t r0, int32_t c0, float padv)
 {
     const LevelK &lv = k.level[0];
@@ -420,7 +420,7 @@ BS_DEV void phase0(const LdsSeqK &k, const TileCtx &t, float *lds, int32_t r0, i
             const int32_t gc = g0 + v * VEC;
             const bool col_in = gc >= 0 && gc < lv.W;  // W % VEC == 0: a vector is all in or all out
             for (int32_t rb = (int32_t)ty; rb < lv.rows; rb += lv.rt * U) {
-                Raw<BF16, VEC> raw[U];
+                Raw<DT, VEC> raw[U];
                 bool inimg[U];
                 uint32_t off[U];
 #pragma unroll
@@ -429,15 +429,15 @@ BS_DEV void phase0(const LdsSeqK &k, const TileCtx &t, float *lds, int32_t r0, i
                     const int32_t gr = r0 + r;
                     inimg[u] = col_in && r < lv.rows && gr >= 0 && gr < lv.H;
                     off[u] = inimg[u] ? gplane + (uint32_t)gr * (uint32_t)lv.W + (uint32_t)gc : 0u;
-                    raw[u] = load_raw<BF16, VEC, true>(k.in, off[u]);
+                    raw[u] = load_raw<DT, VEC, true>(k.in, off[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int32_t r = rb + u * lv.rt;
                     float x[VEC];
-                    unpack<BF16, VEC>(raw[u], x);
+                    unpack<DT, VEC>(raw[u], x);
                     const uint32_t o1[1] = {off[u]};
-                    apply_level_ew<BF16, VEC, true, EW>(x, lv, er, k.res, o1);
+                    apply_level_ew<DT, VEC, true, EW>(x, lv, er, k.res, o1);
                     if (r < lv.rows) {
                         float *d = dplane + r * lv.pitch + v * VEC;
                         if constexpr (VEC >= 4) {
@@ -473,7 +473,7 @@ struct PhaseCtx {
 };
 
 // ---------------- phase l: pooling operation l on the cached level l-1 --------------
-template <bool BF16, class P, class EW, int D, bool WANT_IDX, bool LAST>
+template <int DT, class P, class EW, int D, bool WANT_IDX, bool LAST>
 BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, const LevelK &pv, const P &p,
                        const PhaseCtx &cx)
 {
@@ -507,7 +507,7 @@ BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, con
                 const int32_t gr = cx.r0 + r;
                 if (p.kind() != OP_MAXPOOL) {
 #pragma unroll
-                    for (int e = 0; e < VO; ++e) val[e] = round_store<BF16>(val[e]);
+                    for (int e = 0; e < VO; ++e) val[e] = round_store<DT>(val[e]);
                 }
                 const bool row_in = gr >= 0 && gr < lv.H;
                 const uint32_t goff = gplane + (uint32_t)(row_in ? gr : 0) * (uint32_t)lv.W;
@@ -522,18 +522,18 @@ BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, con
                     uint32_t o4[VO];
 #pragma unroll
                     for (int e = 0; e < VO; ++e) o4[e] = (row_in && cin[e]) ? goff + (uint32_t)(gc + e) : 0u;
-                    apply_level_ew<BF16, VO, false, EW>(val, lv, er, k.res, o4);
+                    apply_level_ew<DT, VO, false, EW>(val, lv, er, k.res, o4);
                 }
                 if (LAST) {
                     if (row_in && gr < cx.end_r) {
                         if (strip_vec) {
-                            store_elems<BF16, VO>(k.out, goff + (uint32_t)gc, val);
+                            store_elems<DT, VO>(k.out, goff + (uint32_t)gc, val);
                         } else {
 #pragma unroll
                             for (int e = 0; e < VO; ++e)
                                 if (cin[e] && gc + e < cx.end_c) {
                                     const float one[1] = {val[e]};
-                                    store_elems<BF16, 1>(k.out, goff + (uint32_t)(gc + e), one);
+                                    store_elems<DT, 1>(k.out, goff + (uint32_t)(gc + e), one);
                                 }
                         }
                     }
@@ -614,7 +614,7 @@ BS_DEV PhaseCtx phase_ctx(const LdsSeqK &k, const TileCtx &t, float *lds, int32_
 // =============================================================================
 // Run-time build: any sequence.
 // =============================================================================
-template <bool BF16, int VEC>
+template <int DT, int VEC>
 __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
 {
     extern __shared__ __align__(16) float lds[];
@@ -623,18 +623,18 @@ __global__ __launch_bounds__(512) void lds_tile_kernel(const LdsSeqK k)
     {
         int32_t r0 = t.ti * k.TH, c0 = t.tj * k.TW;
         for (int32_t l = L; l >= 1; --l) origin_step(k.pool[l], r0, c0);
-        phase0<BF16, VEC, EwList<-1>>(k, t, lds, r0, c0, pad_value(PoolDyn(k.pool[1])));
+        phase0<DT, VEC, EwList<-1>>(k, t, lds, r0, c0, pad_value(PoolDyn(k.pool[1])));
     }
     __syncthreads();
     for (int32_t l = 1; l <= L; ++l) {
         const PhaseCtx cx = phase_ctx(k, t, lds, l);
         const PoolDyn p(k.pool[l]);
         if (cx.last) {
-            if (cx.idxp) pool_phase<BF16, PoolDyn, EwList<-1>, 0, true, true>(k, t, k.level[l], k.level[l - 1], p, cx);
-            else pool_phase<BF16, PoolDyn, EwList<-1>, 0, false, true>(k, t, k.level[l], k.level[l - 1], p, cx);
+            if (cx.idxp) pool_phase<DT, PoolDyn, EwList<-1>, 0, true, true>(k, t, k.level[l], k.level[l - 1], p, cx);
+            else pool_phase<DT, PoolDyn, EwList<-1>, 0, false, true>(k, t, k.level[l], k.level[l - 1], p, cx);
         } else {
-            if (cx.idxp) pool_phase<BF16, PoolDyn, EwList<-1>, 0, true, false>(k, t, k.level[l], k.level[l - 1], p, cx);
-            else pool_phase<BF16, PoolDyn, EwList<-1>, 0, false, false>(k, t, k.level[l], k.level[l - 1], p, cx);
+            if (cx.idxp) pool_phase<DT, PoolDyn, EwList<-1>, 0, true, false>(k, t, k.level[l], k.level[l - 1], p, cx);
+            else pool_phase<DT, PoolDyn, EwList<-1>, 0, false, false>(k, t, k.level[l], k.level[l - 1], p, cx);
             __syncthreads();
         }
     }
@@ -662,23 +662,23 @@ constexpr int sig_delta0()
 }
 
 // phases L, L + 1, ... of a signature, a barrier between them
-template <bool BF16, bool WANT_IDX, int L, int D0, class... Ls>
+template <int DT, bool WANT_IDX, int L, int D0, class... Ls>
 struct SigPhases {
     BS_DEV static void run(const LdsSeqK &, const TileCtx &, float *) {}
 };
-template <bool BF16, bool WANT_IDX, int L, int D0, class L1, class... Rest>
-struct SigPhases<BF16, WANT_IDX, L, D0, L1, Rest...> {
+template <int DT, bool WANT_IDX, int L, int D0, class L1, class... Rest>
+struct SigPhases<DT, WANT_IDX, L, D0, L1, Rest...> {
     BS_DEV static void run(const LdsSeqK &k, const TileCtx &t, float *lds)
     {
         constexpr bool LAST = sizeof...(Rest) == 0;
         PhaseCtx cx = phase_ctx(k, t, lds, L);
         if (L == 1) cx.d_lo = D0;  // compile-time; the planner's argument block carries the same value
         const typename L1::P p(k.pool[L]);
-        pool_phase<BF16, typename L1::P, typename L1::EW, (L == 1 ? (D0 & 3) : 0), WANT_IDX, LAST>(
+        pool_phase<DT, typename L1::P, typename L1::EW, (L == 1 ? (D0 & 3) : 0), WANT_IDX, LAST>(
             k, t, k.level[L], k.level[L - 1], p, cx);
         if constexpr (!LAST) {
             __syncthreads();
-            SigPhases<BF16, WANT_IDX, L + 1, D0, Rest...>::run(k, t, lds);
+            SigPhases<DT, WANT_IDX, L + 1, D0, Rest...>::run(k, t, lds);
         }
     }
 };
@@ -688,7 +688,7 @@ struct FirstLvl {
     using type = L1;
 };
 
-template <bool BF16, int VEC, bool WANT_IDX, int EW0, class... Ls>
+template <int DT, int VEC, bool WANT_IDX, int EW0, class... Ls>
 __global__ __launch_bounds__(512) void lds_sig_kernel(const LdsSeqK k)
 {
     extern __shared__ __align__(16) float lds[];
@@ -699,10 +699,10 @@ __global__ __launch_bounds__(512) void lds_sig_kernel(const LdsSeqK k)
         int32_t r0 = t.ti * k.TH, c0 = t.tj * k.TW;
 #pragma unroll
         for (int l = NL; l >= 1; --l) origin_step(k.pool[l], r0, c0);
-        phase0<BF16, VEC, EwList<EW0>>(k, t, lds, r0, c0, pad_value(typename FirstLvl<Ls...>::type::P(k.pool[1])));
+        phase0<DT, VEC, EwList<EW0>>(k, t, lds, r0, c0, pad_value(typename FirstLvl<Ls...>::type::P(k.pool[1])));
     }
     __syncthreads();
-    SigPhases<BF16, WANT_IDX, 1, D0, Ls...>::run(k, t, lds);
+    SigPhases<DT, WANT_IDX, 1, D0, Ls...>::run(k, t, lds);
 }
 
 // =============================================================================
@@ -711,7 +711,7 @@ __global__ __launch_bounds__(512) void lds_sig_kernel(const LdsSeqK k)
 // signature build's.  The first phase reads the level-0 rows, whose rectangle starts
 // delta0 & 3 floats into an aligned vector: one instance per value.
 // =============================================================================
-template <bool BF16, int VEC, bool WANT_IDX, int EW0, class LV>
+template <int DT, int VEC, bool WANT_IDX, int EW0, class LV>
 __global__ __launch_bounds__(512) void lds_rep_kernel(const LdsSeqK k)
 {
     extern __shared__ __align__(16) float lds[];
@@ -722,7 +722,7 @@ __global__ __launch_bounds__(512) void lds_rep_kernel(const LdsSeqK k)
     {
         int32_t r0 = t.ti * k.TH, c0 = t.tj * k.TW;
         for (int32_t l = L; l >= 1; --l) origin_step(k.pool[l], r0, c0);
-        phase0<BF16, VEC, EwList<EW0>>(k, t, lds, r0, c0, pad_value(P(k.pool[1])));
+        phase0<DT, VEC, EwList<EW0>>(k, t, lds, r0, c0, pad_value(P(k.pool[1])));
     }
     __syncthreads();
     for (int32_t l = 1; l <= L; ++l) {
@@ -731,15 +731,15 @@ __global__ __launch_bounds__(512) void lds_rep_kernel(const LdsSeqK k)
         const LevelK &lv = k.level[l], &pv = k.level[l - 1];
         const int32_t d = cx.d_lo & 3;
         if (cx.last) {
-            if (d == 0) pool_phase<BF16, P, EW, 0, WANT_IDX, true>(k, t, lv, pv, p, cx);
-            else if (d == 1) pool_phase<BF16, P, EW, 1, WANT_IDX, true>(k, t, lv, pv, p, cx);
-            else if (d == 2) pool_phase<BF16, P, EW, 2, WANT_IDX, true>(k, t, lv, pv, p, cx);
-            else pool_phase<BF16, P, EW, 3, WANT_IDX, true>(k, t, lv, pv, p, cx);
+            if (d == 0) pool_phase<DT, P, EW, 0, WANT_IDX, true>(k, t, lv, pv, p, cx);
+            else if (d == 1) pool_phase<DT, P, EW, 1, WANT_IDX, true>(k, t, lv, pv, p, cx);
+            else if (d == 2) pool_phase<DT, P, EW, 2, WANT_IDX, true>(k, t, lv, pv, p, cx);
+            else pool_phase<DT, P, EW, 3, WANT_IDX, true>(k, t, lv, pv, p, cx);
         } else {
-            if (d == 0) pool_phase<BF16, P, EW, 0, WANT_IDX, false>(k, t, lv, pv, p, cx);
-            else if (d == 1) pool_phase<BF16, P, EW, 1, WANT_IDX, false>(k, t, lv, pv, p, cx);
-            else if (d == 2) pool_phase<BF16, P, EW, 2, WANT_IDX, false>(k, t, lv, pv, p, cx);
-            else pool_phase<BF16, P, EW, 3, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            if (d == 0) pool_phase<DT, P, EW, 0, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            else if (d == 1) pool_phase<DT, P, EW, 1, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            else if (d == 2) pool_phase<DT, P, EW, 2, WANT_IDX, false>(k, t, lv, pv, p, cx);
+            else pool_phase<DT, P, EW, 3, WANT_IDX, false>(k, t, lv, pv, p, cx);
             __syncthreads();
         }
     }

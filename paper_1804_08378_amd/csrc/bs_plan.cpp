@@ -244,7 +244,7 @@ static bool covers_input(const Op &op)
     return ok(op.in_h, op.kh, op.sh, op.ph) && ok(op.in_w, op.kw, op.sw, op.pw);
 }
 
-static int32_t vec_of(const bs_stack *s) { return s->dtype == BS_BF16 ? 8 : 4; }
+static int32_t vec_of(const bs_stack *s) { return s->dtype == BS_F32 ? 4 : 8; }
 
 struct SeqDraft {
     int32_t first_step, n_steps;
@@ -522,7 +522,7 @@ static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
         }
     }
     if (seen != 2) return false;
-    if (!rows2_supported(k) && !(jit_allowed(s) && rows2_buildable(k, vec))) return false;
+    if (!(dtype_has_tables(s->dtype) && rows2_supported(k)) && !(jit_allowed(s) && rows2_buildable(k, vec))) return false;
     // every output column must fall under some lane's column block
     const int32_t sws = k.pool1.sw * k.pool2.sw;
     if (vec % sws != 0 || (int64_t)(k.W / vec) * (vec / sws) < k.Wo) return false;
@@ -560,7 +560,7 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
         }
     }
     if (!seen) return false;
-    if (!rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post) &&
+    if (!(dtype_has_tables(s->dtype) && rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) &&
         !(jit_allowed(s) && rows_buildable(k.pool, k.pre, k.n_pre, k.post, k.n_post, vec)))
         return false;
     // every output column must fall under some lane's column block
@@ -668,6 +668,7 @@ static bool seq_is_fast(const bs_stack *s, int32_t first_op, int32_t n_ops)
         return true;
     if (!seq_capacity_ok(s, first_op, n_ops, false)) return false;
     if (jit_allowed(s)) return true;  // any signature gets its own build
+    if (!dtype_has_tables(s->dtype)) return false;
     Sequence tmp;
     LdsSeqK k{};
     int level = 0;
@@ -887,11 +888,10 @@ static bool audit_lds(const Sequence &q)
 // Header and template-instance names (without / with index outputs) of a sequence's run-time build.
 static const char *jit_names(const bs_stack *s, const Sequence &q, std::string (&expr)[2])
 {
-    const bool bf16 = s->dtype == BS_BF16;
     for (int w = 0; w < 2; ++w) {
-        if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) expr[w] = rows2_expr(q.rows2, bf16, w != 0);
-        else if (q.variant == BS_VARIANT_POOL_ROWS) expr[w] = rows_expr(q.rows, bf16, w != 0);
-        else expr[w] = lds_expr(q.lds, bf16, w != 0);
+        if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) expr[w] = rows2_expr(q.rows2, s->dtype, w != 0);
+        else if (q.variant == BS_VARIANT_POOL_ROWS) expr[w] = rows_expr(q.rows, s->dtype, w != 0);
+        else expr[w] = lds_expr(q.lds, s->dtype, w != 0);
     }
     return q.variant == BS_VARIANT_POOL_ROWS ? "bs_rows_device.h" : "bs_lds_device.h";
 }
@@ -903,14 +903,14 @@ static bs_status prepare_jit(bs_stack *s, Sequence &q, bool host_only)
 {
     q.jit = 0;
     q.jit_fn[0] = q.jit_fn[1] = nullptr;
-    const bool bf16 = s->dtype == BS_BF16;
+    const bool tables = dtype_has_tables(s->dtype);
     if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) {
-        if (rows2_supported(q.rows2)) return BS_OK;
+        if (tables && rows2_supported(q.rows2)) return BS_OK;
     } else if (q.variant == BS_VARIANT_POOL_ROWS) {
         const PoolRowsK &k = q.rows;
-        if (rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) return BS_OK;
+        if (tables && rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) return BS_OK;
     } else if (q.variant == BS_VARIANT_LDS_TILE) {
-        if (lds_precompiled(q.lds, bf16) || !jit_allowed(s) || !lds_buildable(q.lds)) return BS_OK;
+        if (lds_precompiled(q.lds, s->dtype) || !jit_allowed(s) || !lds_buildable(q.lds)) return BS_OK;
     } else {
         return BS_OK;
     }

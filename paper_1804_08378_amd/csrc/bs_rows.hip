@@ -57,15 +57,16 @@ static std::string spec_expr(const PoolK &p)
     return b;
 }
 
-std::string rows_expr(const PoolRowsK &k, bool bf16, bool want_idx)
+std::string rows_expr(const PoolRowsK &k, int32_t dtype, bool want_idx)
 {
     char b[96];
     std::snprintf(b, sizeof b, ", %d, %d, %s, %d>", rows_ew_code(k.pre, k.n_pre), rows_ew_code(k.post, k.n_post),
                   want_idx ? "true" : "false", K_ROWS_OR);
-    return std::string("bs::pool_rows_kernel<") + (bf16 ? "true, 8, " : "false, 4, ") + spec_expr(k.pool) + b;
+    return std::string("bs::pool_rows_kernel<") + std::to_string(dtype) + (dtype == BS_F32 ? ", 4, " : ", 8, ") +
+           spec_expr(k.pool) + b;
 }
 
-template <bool BF16, int VEC>
+template <int DT, int VEC>
 static bool rows_launch_t(const PoolRowsK &k, bool want_idx, dim3 grid, dim3 block, hipStream_t st)
 {
     const int cp = rows_ew_code(k.pre, k.n_pre), cq = rows_ew_code(k.post, k.n_post);
@@ -73,19 +74,20 @@ static bool rows_launch_t(const PoolRowsK &k, bool want_idx, dim3 grid, dim3 blo
         using P = decltype(spec);
         constexpr int PC = decltype(pc)::value, QC = decltype(qc)::value;
         if (!rows_pool_is<P>(k.pool) || cp != PC || cq != QC) return false;
-        if (want_idx) pool_rows_kernel<BF16, VEC, P, PC, QC, true, K_ROWS_OR><<<grid, block, 0, st>>>(k);
-        else pool_rows_kernel<BF16, VEC, P, PC, QC, false, K_ROWS_OR><<<grid, block, 0, st>>>(k);
+        if (want_idx) pool_rows_kernel<DT, VEC, P, PC, QC, true, K_ROWS_OR><<<grid, block, 0, st>>>(k);
+        else pool_rows_kernel<DT, VEC, P, PC, QC, false, K_ROWS_OR><<<grid, block, 0, st>>>(k);
         return true;
     });
 }
 
-bs_status launch_rows(const PoolRowsK &k, bool bf16, int64_t grid_n, int32_t threads, void *stream)
+bs_status launch_rows(const PoolRowsK &k, int32_t dtype, int64_t grid_n, int32_t threads, void *stream)
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
     const bool want_idx = k.idx != nullptr && k.pool.kind == OP_MAXPOOL;
-    const bool ok = bf16 ? rows_launch_t<true, 8>(k, want_idx, grid, block, st)
-                         : rows_launch_t<false, 4>(k, want_idx, grid, block, st);
+    if (!dtype_has_tables(dtype)) return BS_ERR_UNSUPPORTED;
+    const bool ok = dtype == BS_BF16 ? rows_launch_t<DT_BF16, 8>(k, want_idx, grid, block, st)
+                                     : rows_launch_t<DT_F32, 4>(k, want_idx, grid, block, st);
     return ok ? BS_OK : BS_ERR_UNSUPPORTED;
 }
 

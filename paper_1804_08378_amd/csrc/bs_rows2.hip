@@ -48,20 +48,20 @@ bool rows2_buildable(const PoolRows2K &k, int32_t vec)
     return r0 * nc0 + b.kh * nc1 <= 160;
 }
 
-std::string rows2_expr(const PoolRows2K &k, bool bf16, bool want_idx)
+std::string rows2_expr(const PoolRows2K &k, int32_t dtype, bool want_idx)
 {
     char b[400];
     const PoolK &p = k.pool1, &q = k.pool2;
     std::snprintf(b, sizeof b,
-                  "bs::pool_rows2_kernel<%s, bs::RowsSpec<%d, %d, %d, %d, %d, %d, %d>, "
+                  "bs::pool_rows2_kernel<%d, %d, bs::RowsSpec<%d, %d, %d, %d, %d, %d, %d>, "
                   "bs::RowsSpec<%d, %d, %d, %d, %d, %d, %d>, %d, %d, %d, %s>",
-                  bf16 ? "true, 8" : "false, 4", p.kind, p.kh, p.kw, p.sh, p.sw, p.ph, p.pw, q.kind, q.kh, q.kw, q.sh,
+                  dtype, dtype == BS_F32 ? 4 : 8, p.kind, p.kh, p.kw, p.sh, p.sw, p.ph, p.pw, q.kind, q.kh, q.kw, q.sh,
                   q.sw, q.ph, q.pw, rows_ew_code(k.pre, k.n_pre), rows_ew_code(k.mid, k.n_mid),
                   rows_ew_code(k.post, k.n_post), want_idx ? "true" : "false");
     return b;
 }
 
-template <bool BF16, int VEC>
+template <int DT, int VEC>
 static bool rows2_launch_t(const PoolRows2K &k, bool want_idx, dim3 grid, dim3 block, hipStream_t st)
 {
     const int c0 = rows_ew_code(k.pre, k.n_pre), c1 = rows_ew_code(k.mid, k.n_mid), c2 = rows_ew_code(k.post, k.n_post);
@@ -70,19 +70,20 @@ static bool rows2_launch_t(const PoolRows2K &k, bool want_idx, dim3 grid, dim3 b
         using P2 = decltype(s2);
         constexpr int C0 = decltype(e0)::value, C1 = decltype(e1)::value, C2 = decltype(e2)::value;
         if (!rows_pool_is<P1>(k.pool1) || !rows_pool_is<P2>(k.pool2) || c0 != C0 || c1 != C1 || c2 != C2) return false;
-        if (want_idx) pool_rows2_kernel<BF16, VEC, P1, P2, C0, C1, C2, true><<<grid, block, 0, st>>>(k);
-        else pool_rows2_kernel<BF16, VEC, P1, P2, C0, C1, C2, false><<<grid, block, 0, st>>>(k);
+        if (want_idx) pool_rows2_kernel<DT, VEC, P1, P2, C0, C1, C2, true><<<grid, block, 0, st>>>(k);
+        else pool_rows2_kernel<DT, VEC, P1, P2, C0, C1, C2, false><<<grid, block, 0, st>>>(k);
         return true;
     });
 }
 
-bs_status launch_rows2(const PoolRows2K &k, bool bf16, int64_t grid_n, int32_t threads, void *stream)
+bs_status launch_rows2(const PoolRows2K &k, int32_t dtype, int64_t grid_n, int32_t threads, void *stream)
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
     const bool want_idx = k.idx != nullptr && k.pool2.kind == OP_MAXPOOL;
-    const bool ok = bf16 ? rows2_launch_t<true, 8>(k, want_idx, grid, block, st)
-                         : rows2_launch_t<false, 4>(k, want_idx, grid, block, st);
+    if (!dtype_has_tables(dtype)) return BS_ERR_UNSUPPORTED;
+    const bool ok = dtype == BS_BF16 ? rows2_launch_t<DT_BF16, 8>(k, want_idx, grid, block, st)
+                                     : rows2_launch_t<DT_F32, 4>(k, want_idx, grid, block, st);
     return ok ? BS_OK : BS_ERR_UNSUPPORTED;
 }
 

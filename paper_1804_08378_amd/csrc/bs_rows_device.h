@@ -57,20 +57,20 @@ BS_DEV void rows_load_params(const EwOp *ew, const float *__restrict__ params, i
 }
 
 // Lists without a residual Add (it would need its own halo loads; such stacks take the LDS path).
-template <bool BF16, class EW, int N>
+template <int DT, class EW, int N>
 BS_DEV void rows_apply(float (&x)[N], const RowsParams<EW> &p)
 {
 #pragma unroll
     for (int j = 0; j < EW::n; ++j) {
         if (EW::kind(j) == OP_BN) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fmaf(x[i], p.sc[j], p.sh[j]));
+            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(__builtin_fmaf(x[i], p.sc[j], p.sh[j]));
         } else if (EW::kind(j) == OP_LEAKY) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(x[i] > 0.0f ? x[i] : x[i] * p.sc[j]);
+            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(x[i] > 0.0f ? x[i] : x[i] * p.sc[j]);
         } else if (EW::kind(j) == OP_CLAMP) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<BF16>(__builtin_fminf(__builtin_fmaxf(x[i], p.sc[j]), p.sh[j]));
+            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(__builtin_fminf(__builtin_fmaxf(x[i], p.sc[j]), p.sh[j]));
         } else {
 #pragma unroll
             for (int i = 0; i < N; ++i) x[i] = __builtin_fmaxf(x[i], 0.0f);  // NaN, -0 -> +0
@@ -121,7 +121,7 @@ inline bool rows_pool_is(const PoolK &q)
 //
 // The pooling shape and the element-wise lists are template arguments; the planner uses this
 // kernel only for the signatures instantiated in the table at the end (rows_supported()).
-template <bool BF16, int VEC, class P, int EWPRE, int EWPOST, bool WANT_IDX, int OR>
+template <int DT, int VEC, class P, int EWPRE, int EWPOST, bool WANT_IDX, int OR>
 __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
 {
     constexpr int KH = P::kh, KW = P::kw, SH = P::sh, SW = P::sw, PH = P::ph, PW = P::pw;
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
     constexpr int WR = KH + (OR - 1) * SH;  // input rows of OR consecutive output rows
     constexpr int ST = OR * SH;             // rows the window slides per iteration
     constexpr int NS = ST < WR ? ST : WR;   // new input rows per iteration
-    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int ES = DT != DT_F32 ? 2 : 4;
     constexpr bool IS_MAX = P::kind == OP_MAXPOOL;
     static_assert(VEC % SW == 0 && NX >= 0 && NL >= 0, "unsupported pooling shape");
     using EWP = RowsEw<EWPRE>;
@@ -163,39 +163,39 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
     for (int n = 0; n < NX; ++n) xin[n] = col0 + VEC + n < k.W;
 
     struct RowRaw {
-        Raw<BF16, VEC> v;
-        Raw<BF16, 1> l[NL > 0 ? NL : 1], x[NX > 0 ? NX : 1];
+        Raw<DT, VEC> v;
+        Raw<DT, 1> l[NL > 0 ? NL : 1], x[NX > 0 ? NX : 1];
         bool ok;
     };
     // issue the loads of input row ih (clamped to a safe address when the row is padding)
     auto fetch = [&](int32_t ih, RowRaw &r) {
         r.ok = ih >= 0 && ih < k.H;
         const uint32_t rowoff = r.ok ? (uint32_t)(ih * k.W) : 0u;
-        r.v = load_raw<BF16, VEC>(inp, rowoff + (uint32_t)col0);
+        r.v = load_raw<DT, VEC>(inp, rowoff + (uint32_t)col0);
 #pragma unroll
-        for (int n = 0; n < NL; ++n) r.l[n] = load_raw<BF16, 1>(inp, lin[n] ? rowoff + (uint32_t)(col0 - NL + n) : 0u);
+        for (int n = 0; n < NL; ++n) r.l[n] = load_raw<DT, 1>(inp, lin[n] ? rowoff + (uint32_t)(col0 - NL + n) : 0u);
 #pragma unroll
-        for (int n = 0; n < NX; ++n) r.x[n] = load_raw<BF16, 1>(inp, xin[n] ? rowoff + (uint32_t)(col0 + VEC + n) : 0u);
+        for (int n = 0; n < NX; ++n) r.x[n] = load_raw<DT, 1>(inp, xin[n] ? rowoff + (uint32_t)(col0 + VEC + n) : 0u);
     };
     // registers -> window row: leading element-wise operations, then padding
     auto settle = [&](const RowRaw &r, float (&w)[NC]) {
         float xv[VEC];
-        unpack<BF16, VEC>(r.v, xv);
+        unpack<DT, VEC>(r.v, xv);
 #pragma unroll
         for (int n = 0; n < VEC; ++n) w[NL + n] = xv[n];
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
             float one[1];
-            unpack<BF16, 1>(r.l[n], one);
+            unpack<DT, 1>(r.l[n], one);
             w[n] = one[0];
         }
 #pragma unroll
         for (int n = 0; n < NX; ++n) {
             float one[1];
-            unpack<BF16, 1>(r.x[n], one);
+            unpack<DT, 1>(r.x[n], one);
             w[NL + VEC + n] = one[0];
         }
-        rows_apply<BF16, EWP, NC>(w, pp);
+        rows_apply<DT, EWP, NC>(w, pp);
 #pragma unroll
         for (int n = 0; n < NL; ++n) w[n] = (r.ok && lin[n]) ? w[n] : padv;
 #pragma unroll
@@ -271,15 +271,15 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
                         const int32_t nc_ = min(w0 + KW, k.W + PW) - w0;
                         inv = 1.0f / (float)max(nr_ * nc_, 1);
                     }
-                    y[e] = round_store<BF16>(sum * inv);
+                    y[e] = round_store<DT>(sum * inv);
                     yi[e] = 0;
                 }
             }
-            rows_apply<BF16, EWQ, VO>(y, qp);
+            rows_apply<DT, EWQ, VO>(y, qp);
             if (oh + o < oh1) {
                 const uint32_t ooff = oplane + (uint32_t)((oh + o) * k.Wo + ow0);
                 if (vec_store) {
-                    store_elems<BF16, VO>(k.out, ooff, y);
+                    store_elems<DT, VO>(k.out, ooff, y);
                     if constexpr (WANT_IDX) {
                         if (k.idx) store_indices<VO>(k.idx + ooff, yi);
                     }
@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
                     for (int e = 0; e < VO; ++e)
                         if (ow0 + e < k.Wo) {
                             const float one[1] = {y[e]};
-                            store_elems<BF16, 1>(k.out, ooff + e, one);
+                            store_elems<DT, 1>(k.out, ooff + e, one);
                             if constexpr (WANT_IDX) {
                                 if (k.idx) k.idx[ooff + e] = yi[e];
                             }
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
 //
 // Cells outside a pooling operation's own input plane are that operation's padding
 // (-inf for max, +0 for average) and are never computed from earlier layers.
-template <bool BF16, int VEC, class P1, class P2, int EW0, int EW1, int EW2, bool WANT_IDX>
+template <int DT, int VEC, class P1, class P2, int EW0, int EW1, int EW2, bool WANT_IDX>
 __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
 {
     constexpr int KH1 = P1::kh, KW1 = P1::kw, SH1 = P1::sh, SW1 = P1::sw, PH1 = P1::ph, PW1 = P1::pw;
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     constexpr int KEEP1 = KH2 - SH2;              // level-1 rows two consecutive output rows share
     constexpr int R0 = (KH2 - 1) * SH1 + KH1;     // level-0 rows under one output row
     constexpr int NS0 = SH1 * SH2;                // new level-0 rows per output row
-    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int ES = DT != DT_F32 ? 2 : 4;
     constexpr bool MAX1 = P1::kind == OP_MAXPOOL, MAX2 = P2::kind == OP_MAXPOOL;
     static_assert(VEC % (SW1 * SW2) == 0 && NX >= 0 && KEEP0 >= 0 && KEEP1 >= 0, "unsupported pooling shapes");
     using E0 = RowsEw<EW0>;
@@ -378,39 +378,39 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     for (int n = 0; n < NC1; ++n) c1in[n] = c1s + n >= 0 && c1s + n < k.W1;
 
     struct RowRaw {
-        Raw<BF16, VEC> v;
-        Raw<BF16, 1> l[NL > 0 ? NL : 1], x[NX > 0 ? NX : 1];
+        Raw<DT, VEC> v;
+        Raw<DT, 1> l[NL > 0 ? NL : 1], x[NX > 0 ? NX : 1];
         bool ok;
     };
     // issue the loads of input row ih (clamped to a safe address when the row is padding)
     auto fetch = [&](int32_t ih, RowRaw &r) {
         r.ok = ih >= 0 && ih < k.H;
         const uint32_t rowoff = r.ok ? (uint32_t)(ih * k.W) : 0u;
-        r.v = load_raw<BF16, VEC>(inp, rowoff + (uint32_t)col0);
+        r.v = load_raw<DT, VEC>(inp, rowoff + (uint32_t)col0);
 #pragma unroll
-        for (int n = 0; n < NL; ++n) r.l[n] = load_raw<BF16, 1>(inp, lin[n] ? rowoff + (uint32_t)(col0 - NL + n) : 0u);
+        for (int n = 0; n < NL; ++n) r.l[n] = load_raw<DT, 1>(inp, lin[n] ? rowoff + (uint32_t)(col0 - NL + n) : 0u);
 #pragma unroll
-        for (int n = 0; n < NX; ++n) r.x[n] = load_raw<BF16, 1>(inp, xin[n] ? rowoff + (uint32_t)(col0 + VEC + n) : 0u);
+        for (int n = 0; n < NX; ++n) r.x[n] = load_raw<DT, 1>(inp, xin[n] ? rowoff + (uint32_t)(col0 + VEC + n) : 0u);
     };
     // registers -> level-0 row: leading element-wise operations, then the first pool's padding
     auto settle = [&](const RowRaw &r, float (&w)[NC0]) {
         float xv[VEC];
-        unpack<BF16, VEC>(r.v, xv);
+        unpack<DT, VEC>(r.v, xv);
 #pragma unroll
         for (int n = 0; n < VEC; ++n) w[NL + n] = xv[n];
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
             float one[1];
-            unpack<BF16, 1>(r.l[n], one);
+            unpack<DT, 1>(r.l[n], one);
             w[n] = one[0];
         }
 #pragma unroll
         for (int n = 0; n < NX; ++n) {
             float one[1];
-            unpack<BF16, 1>(r.x[n], one);
+            unpack<DT, 1>(r.x[n], one);
             w[NL + VEC + n] = one[0];
         }
-        rows_apply<BF16, E0, NC0>(w, p0);
+        rows_apply<DT, E0, NC0>(w, p0);
 #pragma unroll
         for (int n = 0; n < NL; ++n) w[n] = (r.ok && lin[n]) ? w[n] : pad0;
 #pragma unroll
@@ -445,10 +445,10 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
                     const int32_t nc_ = padded ? min(w0c + KW1, k.W + PW1) - w0c : min(w0c + KW1, k.W) - max(w0c, 0);
                     inv = 1.0f / (float)max(nr_ * nc_, 1);
                 }
-                y[n] = round_store<BF16>(sum * inv);
+                y[n] = round_store<DT>(sum * inv);
             }
         }
-        rows_apply<BF16, E1, NC1>(y, p1);
+        rows_apply<DT, E1, NC1>(y, p1);
         const bool rok = r1 >= 0 && r1 < k.H1;
 #pragma unroll
         for (int n = 0; n < NC1; ++n) y[n] = (rok && c1in[n]) ? y[n] : pad1;
@@ -525,15 +525,15 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
                     const int32_t nc_ = padded ? min(w0 + KW2, k.W1 + PW2) - w0 : min(w0 + KW2, k.W1) - max(w0, 0);
                     inv = 1.0f / (float)max(nr_ * nc_, 1);
                 }
-                y[e] = round_store<BF16>(sum * inv);
+                y[e] = round_store<DT>(sum * inv);
                 yi[e] = 0;
             }
         }
-        rows_apply<BF16, E2, VO>(y, p2);
+        rows_apply<DT, E2, VO>(y, p2);
         {
             const uint32_t ooff = oplane + (uint32_t)(oh * k.Wo + ow0);
             if (vec_store) {
-                store_elems<BF16, VO, false>(k.out, ooff, y);
+                store_elems<DT, VO, false>(k.out, ooff, y);
                 if constexpr (WANT_IDX) {
                     if (k.idx) store_indices<VO>(k.idx + ooff, yi);
                 }
@@ -542,7 +542,7 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
                 for (int e = 0; e < VO; ++e)
                     if (ow0 + e < k.Wo) {
                         const float one[1] = {y[e]};
-                        store_elems<BF16, 1, false>(k.out, ooff + e, one);
+                        store_elems<DT, 1, false>(k.out, ooff + e, one);
                         if constexpr (WANT_IDX) {
                             if (k.idx) k.idx[ooff + e] = yi[e];
                         }

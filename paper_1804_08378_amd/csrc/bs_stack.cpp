@@ -9,7 +9,7 @@
 
 namespace bs {
 
-size_t dtype_size(int32_t dtype) { return dtype == BS_BF16 ? 2 : 4; }
+size_t dtype_size(int32_t dtype) { return dtype == BS_F32 ? 4 : 2; }
 
 static thread_local int32_t g_last_hip_error = 0;
 void set_hip_error(int32_t e) { g_last_hip_error = e; }
@@ -50,7 +50,7 @@ bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers, const i
 {
     if (!layers || !in_shape || !out) return BS_ERR_NULL;
     if (n_layers < 1 || n_layers > BS_MAX_LAYERS) return BS_ERR_UNSUPPORTED;
-    if (dtype != BS_F32 && dtype != BS_BF16) return BS_ERR_UNSUPPORTED;
+    if (dtype != BS_F32 && dtype != BS_BF16 && dtype != BS_F16) return BS_ERR_UNSUPPORTED;
     for (int i = 0; i < 4; ++i)
         if (in_shape[i] < 1) return BS_ERR_SHAPE;
     const int64_t limit = (1ll << 31) - 1;

@@ -143,9 +143,9 @@ class BrainSlugStack(nn.Module):
         key = (tuple(int(v) for v in shape), dtype)
         st = self._plans.get(key)
         if st is None:
-            name = {torch.float32: "f32", torch.bfloat16: "bf16"}.get(dtype)
+            name = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}.get(dtype)
             if name is None:
-                raise TypeError(f"BrainSlugStack supports float32 and bfloat16 tensors, not {dtype}")
+                raise TypeError(f"BrainSlugStack supports float32, bfloat16 and float16 tensors, not {dtype}")
             st = bs.Stack(resolve_layers(self.layers, key[0]), key[0], name).plan(**self.plan_opts)
             self._plans[key] = st
         return st

@@ -150,9 +150,9 @@ def build(name: str, seed: int = 0, batch: int | None = None, indices: bool = Fa
         return _bn_relu_pool(256, seed, maxpool(2, 2), indices), (nb(32), 256, 56, 56), ("f32",)
     if name == "resnet_stem":  # config 2
         return (_bn_relu_pool(64, seed, maxpool(3, 2, 1), indices), (nb(64), 64, 112, 112),
-                ("f32", "bf16"))
+                ("f32", "bf16", "f16"))
     if name == "resnet_tail":
-        return [bn_params(256, seed + 100), add(), relu()], (nb(64), 256, 56, 56), ("f32", "bf16")
+        return [bn_params(256, seed + 100), add(), relu()], (nb(64), 256, 56, 56), ("f32", "bf16", "f16")
     if name == "densenet_dense":  # config 3
         return [bn_params(256, seed + 100), relu()], (nb(64), 256, 56, 56), ("f32",)
     if name == "densenet_trans":
@@ -160,7 +160,7 @@ def build(name: str, seed: int = 0, batch: int | None = None, indices: bool = Fa
     if name == "halo_stress":  # config 4
         layers = [bn_params(128, seed + 100), relu(), avgpool(3, 1, 1, True),
                   maxpool(3, 2, 1, indices), bn_params(128, seed + 104), relu()]
-        return layers, (nb(128), 128, 56, 56), ("f32", "bf16")
+        return layers, (nb(128), 128, 56, 56), ("f32", "bf16", "f16")
     raise KeyError(name)
 
 

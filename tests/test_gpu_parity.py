@@ -16,14 +16,13 @@ from paper_1804_08378_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 1e-2}
+TOL = {"f32": 1e-5, "bf16": 1e-2, "f16": 1e-3}
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
 
 
 def _dev(a, dtype):
     t = torch.from_numpy(np.ascontiguousarray(a))
-    if dtype == "bf16":
-        t = t.to(torch.bfloat16)  # inputs are bf16-representable: lossless
-    return t.cuda()
+    return t.to(TORCH_DTYPE[dtype]).cuda()  # inputs are representable in the storage type: lossless
 
 
 def run_gpu(layers, x, res, dtype, **opts):
@@ -134,7 +133,7 @@ SHAPES = [(2, 3, 13, 11), (1, 1, 1, 1), (1, 2, 9, 16), (3, 5, 32, 24), (1, 7, 57
 
 
 @pytest.mark.parametrize("shape", SHAPES)
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_ragged_shapes_all_stacks(shape, dtype):
     for name, layers in _stacks(shape[1]).items():
         if wl.output_shape(layers, shape)[2] < 1 or wl.output_shape(layers, shape)[3] < 1:
@@ -264,7 +263,7 @@ def _rows_stacks(c):
 
 
 @pytest.mark.parametrize("shape", [(2, 3, 12, 16), (1, 2, 9, 8), (3, 5, 33, 24), (1, 4, 64, 64), (1, 1, 3, 8)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_pool_rows_kernel(shape, dtype):
     """Single pooling step with overlapping / padded windows through the register-sliding
     rows kernel, for several chunk lengths (1 row per lane, ragged, whole plane)."""
@@ -292,7 +291,7 @@ def _rows2_stacks(c):
 
 @pytest.mark.parametrize("shape", [(2, 3, 12, 16), (1, 2, 9, 8), (3, 5, 33, 24), (1, 4, 64, 64), (1, 1, 3, 8),
                                    (1, 2, 1, 8), (2, 2, 2, 16)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_pool_rows2_kernel(shape, dtype):
     """Two pooling steps in one sequence through the two-level register-sliding kernel, for
     several chunk lengths (1 row per lane, ragged, whole plane), and the same stacks through
@@ -325,7 +324,7 @@ def _built_stacks(c):
 
 
 @pytest.mark.parametrize("shape", [(2, 3, 24, 32), (1, 2, 31, 30), (2, 4, 17, 16)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_run_time_builds(shape, dtype):
     """Stacks whose signature has no pre-compiled kernel get one built at plan time (required
     here: a failed build fails the plan); the result matches the oracle, and so does the same
@@ -395,7 +394,7 @@ def test_random_stacks_match_the_oracle(seed):
         small = seed >= 6
         if small:
             w = int(rng.choice([8, 16, 24, 32, 40, 48]))
-        dtype = "f32" if (seed + case) % 2 == 0 else "bf16"
+        dtype = ("f32", "bf16", "f16")[(seed + case) % 3]
         layers, res_shapes = _random_stack(rng, c, h, w, small)
         x = wl.activation((n, c, h, w), 2000 + 10 * seed + case, dtype)
         res = [wl.activation((n, c) + rs, 3000 + i, dtype) for i, rs in enumerate(res_shapes)]
@@ -463,7 +462,7 @@ def test_run_can_be_captured_in_a_hip_graph_and_replayed():
 
 # ------------------------------------------------------------------ global pooling
 @pytest.mark.parametrize("shape", [(3, 5, 7, 7), (2, 4, 1, 1), (1, 300, 6, 5), (2, 3, 13, 9)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_global_pooling_one_lane_per_plane(shape, dtype):
     """Pools whose window is the whole plane (the head of a network): average and maximum with
     indices, element-wise layers (a residual Add among them) before and after."""
@@ -497,7 +496,7 @@ def _activation_stacks(c):
 
 
 @pytest.mark.parametrize("shape", [(2, 3, 24, 32), (1, 2, 31, 30)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_leaky_relu_and_clamp_in_every_kernel_family(shape, dtype):
     for name, (layers, n_res) in _activation_stacks(shape[1]).items():
         x = wl.activation(shape, 75, dtype) * 3
@@ -506,9 +505,8 @@ def test_leaky_relu_and_clamp_in_every_kernel_family(shape, dtype):
             rshape = wl.output_shape(layers[:[l["kind"] for l in layers].index("add")], shape)
             res = [wl.activation(rshape, 76, dtype)]
         x = np.ascontiguousarray(x.astype(np.float32))
-        if dtype == "bf16":
-            from oracle import layers as OL
-            x = OL.round_bf16(x)
+        from oracle import layers as OL
+        x = OL.round_to(x, dtype)
         check(layers, x, res, dtype, f"act/{name}{shape}")
         check(layers, x, res, dtype, f"act/{name}{shape}/layer-by-layer", breadth_first=1)
         check(layers, x, res, dtype, f"act/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
@@ -531,7 +529,7 @@ def _ceil_stacks(c):
 
 
 @pytest.mark.parametrize("shape", [(2, 3, 18, 24), (1, 2, 21, 21), (2, 2, 13, 16), (1, 4, 8, 8)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_ceil_mode_pools(shape, dtype):
     """Ceil-mode pools: one more, overhanging, window per dimension where the floor-mode windows
     leave cells uncovered; its cells outside the plane count like padding."""

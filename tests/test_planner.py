@@ -48,12 +48,12 @@ def test_run_time_builds_compile_without_a_device():
         # 5x5 windows: a lane of the rows kernel would compute 8 columns for 4 owned (float32) or
         # 12 for 8 (bfloat16); LDS shares them between lanes and wins in the first case
         ([wl.maxpool(5, 1, 2, True), wl.bn_params(4, 0), wl.relu()], (2, 4, 32, 32),
-         {"f32": ["lds_tile"], "bf16": ["pool_rows"]}, 2),
+         {"f32": ["lds_tile"], "bf16": ["pool_rows"], "f16": ["pool_rows"]}, 2),
         ([wl.maxpool(3, 2, 1), wl.bn_params(4, 1), wl.relu(), wl.avgpool(2, 2), wl.maxpool(3, 1, 1)],
          (2, 4, 64, 64), ["lds_tile"], 1),
         ([wl.bn_params(4, 2), wl.add(), wl.relu(), wl.maxpool(3, 2, 1)], (1, 4, 30, 30), ["lds_tile"], 1),
     ]
-    for dt in ("f32", "bf16"):
+    for dt in ("f32", "bf16", "f16"):
         for layers, shape, variants, n_kernels in cases:
             st = bs.Stack(layers, shape, dt).plan(host_only=1, num_cus=256)
             info = st.info()
@@ -62,11 +62,18 @@ def test_run_time_builds_compile_without_a_device():
             assert all(q["run_time_build"] == 1 for q in info["sequences"])
             assert bs.bs_stack_jit_check(st.handle) == n_kernels  # with and without index outputs
             st.close()
-    # the BASELINE stacks need none
+    # the BASELINE stacks need none in float32 / bfloat16; in binary16, which has no signature
+    # tables compiled in, the ResNet stem's sliding-window kernel is a run-time build
     layers, shape, _ = wl.build("vgg_a")
     st = bs.Stack(layers, shape, "f32").plan(host_only=1, num_cus=256)
     assert bs.bs_stack_jit_check(st.handle) == 0
     st.close()
+    layers, shape, _ = wl.build("resnet_stem")
+    for dt, n in (("bf16", 0), ("f16", 1)):
+        st = bs.Stack(layers, shape, dt).plan(host_only=1, num_cus=256)
+        assert st.info()["sequences"][0]["variant_name"] == "pool_rows"
+        assert bs.bs_stack_jit_check(st.handle) == n
+        st.close()
 
 
 def test_step_rule_elementwise_always_joins_second_pool_opens_a_step():
