@@ -49,7 +49,7 @@ class StackBench:
         self.bytes = wl.algorithmic_bytes(layers, x.shape, dtype, indices)
         self.lbl_bytes = wl.layer_by_layer_bytes(layers, x.shape, dtype)
         self.images = x.shape[0]
-        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
         self.fused = bs.Stack(layers, x.shape, dtype).plan(**plan_opts)
         self.lbl = bs.Stack(layers, x.shape, dtype).plan(breadth_first=1)
         self.sets = min(64, max(2, -(-min_rotation_bytes // self.bytes)))
