@@ -402,6 +402,8 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
 
     switch (q.variant) {
     case BS_VARIANT_STREAM: {
+        // vector widths the compiled instances exist for (guards against a plan / kernel mismatch)
+        if (q.vec != 1 && q.vec != (dtype == BS_F32 ? 4 : 8)) return BS_ERR_UNSUPPORTED;
         StreamK k = q.stream;
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
@@ -418,6 +420,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         break;
     }
     case BS_VARIANT_POOL_DIRECT: {
+        if (q.vec != (dtype == BS_F32 ? 4 : 8) || (int64_t)q.direct.div_wv.d * q.vec != q.direct.W) return BS_ERR_UNSUPPORTED;
         PoolDirectK k = q.direct;
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];

@@ -139,6 +139,8 @@ bs_status launch_lds(const LdsSeqK &k, int32_t dtype, int64_t grid_n, int32_t th
     bool want_idx = false;
     for (int l = 1; l <= k.n_levels; ++l)
         if (k.pool[l].idx_slot >= 0 && k.idx[k.pool[l].idx_slot]) want_idx = true;
+    // vector widths the compiled instances exist for (guards against a plan / kernel mismatch)
+    if (k.vec != 1 && k.vec != (dtype == BS_F32 ? 4 : 8)) return BS_ERR_UNSUPPORTED;
     if (dtype == BS_F16) {  // no signature table for binary16: the run-time-shape kernel
         if (k.vec == 8) lds_tile_kernel<DT_F16, 8><<<grid, block, lds, st>>>(k);
         else lds_tile_kernel<DT_F16, 1><<<grid, block, lds, st>>>(k);

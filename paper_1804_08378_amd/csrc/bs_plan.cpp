@@ -904,6 +904,9 @@ static bs_status prepare_jit(bs_stack *s, Sequence &q, bool host_only)
     q.jit = 0;
     q.jit_fn[0] = q.jit_fn[1] = nullptr;
     const bool tables = dtype_has_tables(s->dtype);
+    // the sliding-window kernels (compiled in or built here) are instantiated for one column-block
+    // width per storage type; a plan made for another width must never reach them
+    if (q.variant == BS_VARIANT_POOL_ROWS && q.vec != (s->dtype == BS_F32 ? 4 : 8)) return BS_ERR_UNSUPPORTED;
     if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) {
         if (tables && rows2_supported(q.rows2)) return BS_OK;
     } else if (q.variant == BS_VARIANT_POOL_ROWS) {

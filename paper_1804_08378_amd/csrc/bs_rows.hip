@@ -69,6 +69,8 @@ std::string rows_expr(const PoolRowsK &k, int32_t dtype, bool want_idx)
 template <int DT, int VEC>
 static bool rows_launch_t(const PoolRowsK &k, bool want_idx, dim3 grid, dim3 block, hipStream_t st)
 {
+    // the argument block must have been planned for this instance's column-block width
+    if ((int64_t)k.cbs * VEC != k.W) return false;
     const int cp = rows_ew_code(k.pre, k.n_pre), cq = rows_ew_code(k.post, k.n_post);
     return rows_for_each_signature([&](auto spec, auto pc, auto qc) {
         using P = decltype(spec);

@@ -64,6 +64,8 @@ std::string rows2_expr(const PoolRows2K &k, int32_t dtype, bool want_idx)
 template <int DT, int VEC>
 static bool rows2_launch_t(const PoolRows2K &k, bool want_idx, dim3 grid, dim3 block, hipStream_t st)
 {
+    // the argument block must have been planned for this instance's column-block width
+    if ((int64_t)k.cbs * VEC != k.W) return false;
     const int c0 = rows_ew_code(k.pre, k.n_pre), c1 = rows_ew_code(k.mid, k.n_mid), c2 = rows_ew_code(k.post, k.n_post);
     return rows2_for_each_signature([&](auto s1, auto s2, auto e0, auto e1, auto e2) {
         using P1 = decltype(s1);
