@@ -271,9 +271,9 @@ def main():
     ap.add_argument("--deep", action="store_true",
                     help="also run the stacked-layers experiment of Section 5.1: 1..40 blocks of "
                          "<MaxPool 3/1/1, BatchNorm, ReLU> under the three sequence strategies")
-    ap.add_argument("--one-stream", action="store_true",
-                    help="enqueue all stacks of a step on one stream (default: the three independent stacks "
-                         "of a step go to one HIP stream each, all of default priority)")
+    ap.add_argument("--streams", action="store_true",
+                    help="enqueue the three independent stacks of a step on one HIP stream each (default priority) "
+                         "instead of all on one stream: kernels then overlap at their edges")
     ap.add_argument("--frontend", action="store_true",
                     help="also time the VGG stacks as torch modules: PyTorch eager against frontend.optimize()")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
@@ -312,7 +312,7 @@ def main():
 
     stacks = [StackBench(n, "f32") for n in wl.VGG_STACKS]
     step_bytes = sum(sb.bytes for sb in stacks)
-    streams = None if args.one_stream else [torch.cuda.Stream() for _ in stacks]
+    streams = [torch.cuda.Stream() for _ in stacks] if args.streams else None
     ms, per, mins = time_steps(stacks, "fused", args.steps, args.warmup, streams)
     if args.no_baseline:
         ms_lbl = float("nan")
@@ -330,7 +330,7 @@ def main():
         "config": {"workload": "BASELINE config 1: VGG-16-BN stacks BN->ReLU->MaxPool2x2/2, fp32, "
                                "batch 32, 64x224x224 + 128x112x112 + 256x56x56, indices off",
                    "rotation_sets": [sb.sets for sb in stacks],
-                   "streams": 1 if args.one_stream else len(stacks)},
+                   "streams": len(stacks) if args.streams else 1},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "images_per_s": round(dom.images / (ms * 1e-3), 1),
         "speedup_vs_layer_by_layer": None if args.no_baseline else round(ms_lbl / ms, 3),
