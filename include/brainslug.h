@@ -58,7 +58,8 @@ typedef enum bs_status {
     BS_ERR_ALLOC = 10,      /* host allocation failed                                      */
     BS_ERR_RANGE = 11,      /* an index argument is out of range                           */
     BS_ERR_ALIAS = 12,      /* out overlaps an input where that is not allowed             */
-    BS_ERR_JIT = 13         /* a run-time kernel build the caller required has failed      */
+    BS_ERR_JIT = 13,        /* a run-time kernel build the caller required has failed      */
+    BS_ERR_DEVICE = 14      /* the current HIP device is not the one the stack was planned on */
 } bs_status;
 
 /* Storage type of every tensor of a stack; the arithmetic is float32 for all three, each
@@ -266,7 +267,9 @@ BS_API uint64_t bs_stack_workspace_bytes(const bs_stack *stack);
  *              the array or single entries may be NULL to skip those outputs
  *   workspace  device, >= bs_stack_workspace_bytes() (NULL allowed when that is 0)
  * All device pointers must be 16-byte aligned.
- * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED, BS_ERR_ALIGN, BS_ERR_WORKSPACE,
+ * The device that was current in bs_stack_plan (it holds the parameter table and the kernels
+ * built for the stack) must be current again.
+ * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED, BS_ERR_DEVICE, BS_ERR_ALIGN, BS_ERR_WORKSPACE,
  *         BS_ERR_ALIAS, BS_ERR_HIP (launch failure; raw code in bs_last_hip_error()).
  */
 BS_API bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,

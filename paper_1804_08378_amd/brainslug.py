@@ -25,7 +25,7 @@ VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows", 5
 STATUS_NAMES = {
     0: "BS_OK", 1: "BS_ERR_NULL", 2: "BS_ERR_SHAPE", 3: "BS_ERR_PARAM", 4: "BS_ERR_UNSUPPORTED",
     5: "BS_ERR_NOT_PLANNED", 6: "BS_ERR_NO_FIT", 7: "BS_ERR_ALIGN", 8: "BS_ERR_WORKSPACE",
-    9: "BS_ERR_HIP", 10: "BS_ERR_ALLOC", 11: "BS_ERR_RANGE", 12: "BS_ERR_ALIAS", 13: "BS_ERR_JIT",
+    9: "BS_ERR_HIP", 10: "BS_ERR_ALLOC", 11: "BS_ERR_RANGE", 12: "BS_ERR_ALIAS", 13: "BS_ERR_JIT", 14: "BS_ERR_DEVICE",
 }
 
 _f32p = C.POINTER(C.c_float)

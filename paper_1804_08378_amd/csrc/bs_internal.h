@@ -109,6 +109,7 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
 
 // device side (bs_kernels.hip)
 bs_status device_limits(Limits *lim, int *device);
+int current_device();  // -1 if it cannot be queried
 bs_status upload_params(bs_stack *s);
 void free_params(bs_stack *s);
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,

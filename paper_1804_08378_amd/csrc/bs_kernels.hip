@@ -328,6 +328,16 @@ bs_status device_limits(Limits *lim, int *device)
     return BS_OK;
 }
 
+int current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    return dev;
+}
+
 bs_status upload_params(bs_stack *s)
 {
     free_params(s);

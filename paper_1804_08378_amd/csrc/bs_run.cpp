@@ -24,6 +24,7 @@ extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const v
 {
     if (!stack || !in || !out) return BS_ERR_NULL;
     if (!stack->planned || !stack->device_planned) return BS_ERR_NOT_PLANNED;
+    if (current_device() != stack->device) return BS_ERR_DEVICE;
     if (stack->n_res > 0 && !residuals) return BS_ERR_NULL;
     for (int32_t i = 0; i < stack->n_res; ++i)
         if (!residuals[i]) return BS_ERR_NULL;

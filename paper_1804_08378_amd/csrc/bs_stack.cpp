@@ -223,6 +223,7 @@ const char *bs_status_string(bs_status status)
     case BS_ERR_RANGE: return "index out of range";
     case BS_ERR_ALIAS: return "output overlaps an input";
     case BS_ERR_JIT: return "run-time kernel build failed";
+    case BS_ERR_DEVICE: return "current device is not the device the stack was planned on";
     }
     return "unknown status";
 }
