@@ -47,6 +47,11 @@ constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
 constexpr int K_STREAM_U = 4;     // 128-bit vectors per lane in stream_kernel
 constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
+// Elements per lane and row (the lane's column block) of the sliding-window kernels for 16-bit
+// storage: one 128-bit load, as for float32 (4).  Measured on MI355X, 64-bit blocks (twice the
+// lanes) are 15..30 % slower for the one-level kernel.
+constexpr int K_ROWS_VEC16 = 8;
+constexpr int K_ROWS2_VEC16 = 8;
 constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
 

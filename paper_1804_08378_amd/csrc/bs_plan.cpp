@@ -496,7 +496,7 @@ static bool rows_columns_pay(const bs_stack *s, int32_t nc0, int32_t vec)
 // the first, in shapes the two-level rows kernel is instantiated for (or can be built for).
 static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
 {
-    const int32_t vec = vec_of(s);
+    const int32_t vec = rows2_vec(s->dtype);
     Sequence tmp;
     Sequence &q = fill ? *fill : tmp;
     PoolRows2K k{};
@@ -540,7 +540,7 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
 {
     if (count_pools(s, first_op, n_ops) == 2) return rows2_applicable(s, first_op, n_ops, fill);
     if (count_pools(s, first_op, n_ops) != 1) return false;
-    const int32_t vec = vec_of(s);
+    const int32_t vec = rows_vec(s->dtype);
     Sequence tmp;
     Sequence &q = fill ? *fill : tmp;
     PoolRowsK k{};
@@ -573,7 +573,7 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
 static void plan_rows2(const bs_stack *s, Sequence &q, const bs_plan_options &o)
 {
     PoolRows2K &k = q.rows2;
-    const int32_t vec = vec_of(s);
+    const int32_t vec = rows2_vec(s->dtype);
     q.vec = vec;
     q.threads = std::min(q.threads, 256);
     k.C = (int32_t)q.in_shape[1];
@@ -619,7 +619,7 @@ static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, 
         return;
     }
     PoolRowsK &k = q.rows;
-    const int32_t vec = vec_of(s);
+    const int32_t vec = rows_vec(s->dtype);
     q.vec = vec;
     q.threads = std::min(q.threads, 256);
     k.C = (int32_t)q.in_shape[1];
@@ -906,7 +906,8 @@ static bs_status prepare_jit(bs_stack *s, Sequence &q, bool host_only)
     const bool tables = dtype_has_tables(s->dtype);
     // the sliding-window kernels (compiled in or built here) are instantiated for one column-block
     // width per storage type; a plan made for another width must never reach them
-    if (q.variant == BS_VARIANT_POOL_ROWS && q.vec != (s->dtype == BS_F32 ? 4 : 8)) return BS_ERR_UNSUPPORTED;
+    if (q.variant == BS_VARIANT_POOL_ROWS && q.vec != (q.n_levels == 2 ? rows2_vec(s->dtype) : rows_vec(s->dtype)))
+        return BS_ERR_UNSUPPORTED;
     if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) {
         if (tables && rows2_supported(q.rows2)) return BS_OK;
     } else if (q.variant == BS_VARIANT_POOL_ROWS) {

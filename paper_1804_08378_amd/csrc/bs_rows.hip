@@ -62,7 +62,7 @@ std::string rows_expr(const PoolRowsK &k, int32_t dtype, bool want_idx)
     char b[96];
     std::snprintf(b, sizeof b, ", %d, %d, %s, %d>", rows_ew_code(k.pre, k.n_pre), rows_ew_code(k.post, k.n_post),
                   want_idx ? "true" : "false", K_ROWS_OR);
-    return std::string("bs::pool_rows_kernel<") + std::to_string(dtype) + (dtype == BS_F32 ? ", 4, " : ", 8, ") +
+    return std::string("bs::pool_rows_kernel<") + std::to_string(dtype) + ", " + std::to_string(rows_vec(dtype)) + ", " +
            spec_expr(k.pool) + b;
 }
 
@@ -88,7 +88,7 @@ bs_status launch_rows(const PoolRowsK &k, int32_t dtype, int64_t grid_n, int32_t
     const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
     const bool want_idx = k.idx != nullptr && k.pool.kind == OP_MAXPOOL;
     if (!dtype_has_tables(dtype)) return BS_ERR_UNSUPPORTED;
-    const bool ok = dtype == BS_BF16 ? rows_launch_t<DT_BF16, 8>(k, want_idx, grid, block, st)
+    const bool ok = dtype == BS_BF16 ? rows_launch_t<DT_BF16, K_ROWS_VEC16>(k, want_idx, grid, block, st)
                                      : rows_launch_t<DT_F32, 4>(k, want_idx, grid, block, st);
     return ok ? BS_OK : BS_ERR_UNSUPPORTED;
 }

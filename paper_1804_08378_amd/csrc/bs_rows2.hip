@@ -55,7 +55,7 @@ std::string rows2_expr(const PoolRows2K &k, int32_t dtype, bool want_idx)
     std::snprintf(b, sizeof b,
                   "bs::pool_rows2_kernel<%d, %d, bs::RowsSpec<%d, %d, %d, %d, %d, %d, %d>, "
                   "bs::RowsSpec<%d, %d, %d, %d, %d, %d, %d>, %d, %d, %d, %s>",
-                  dtype, dtype == BS_F32 ? 4 : 8, p.kind, p.kh, p.kw, p.sh, p.sw, p.ph, p.pw, q.kind, q.kh, q.kw, q.sh,
+                  dtype, rows2_vec(dtype), p.kind, p.kh, p.kw, p.sh, p.sw, p.ph, p.pw, q.kind, q.kh, q.kw, q.sh,
                   q.sw, q.ph, q.pw, rows_ew_code(k.pre, k.n_pre), rows_ew_code(k.mid, k.n_mid),
                   rows_ew_code(k.post, k.n_post), want_idx ? "true" : "false");
     return b;
@@ -84,7 +84,7 @@ bs_status launch_rows2(const PoolRows2K &k, int32_t dtype, int64_t grid_n, int32
     const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
     const bool want_idx = k.idx != nullptr && k.pool2.kind == OP_MAXPOOL;
     if (!dtype_has_tables(dtype)) return BS_ERR_UNSUPPORTED;
-    const bool ok = dtype == BS_BF16 ? rows2_launch_t<DT_BF16, 8>(k, want_idx, grid, block, st)
+    const bool ok = dtype == BS_BF16 ? rows2_launch_t<DT_BF16, K_ROWS2_VEC16>(k, want_idx, grid, block, st)
                                      : rows2_launch_t<DT_F32, 4>(k, want_idx, grid, block, st);
     return ok ? BS_OK : BS_ERR_UNSUPPORTED;
 }

@@ -46,7 +46,7 @@ def test_run_time_builds_compile_without_a_device():
     cases = [
         ([wl.bn_params(4, 0), wl.relu(), wl.maxpool((3, 2), (1, 2), (1, 0), True)], (2, 4, 32, 32), ["pool_rows"], 2),
         # 5x5 windows: a lane of the rows kernel would compute 8 columns for 4 owned (float32) or
-        # 12 for 8 (bfloat16); LDS shares them between lanes and wins in the first case
+        # 12 for 8 (16-bit types); LDS shares them between lanes and wins in the first case
         ([wl.maxpool(5, 1, 2, True), wl.bn_params(4, 0), wl.relu()], (2, 4, 32, 32),
          {"f32": ["lds_tile"], "bf16": ["pool_rows"], "f16": ["pool_rows"]}, 2),
         ([wl.maxpool(3, 2, 1), wl.bn_params(4, 1), wl.relu(), wl.avgpool(2, 2), wl.maxpool(3, 1, 1)],
