@@ -103,7 +103,7 @@ size_t dtype_size(int32_t dtype);
 inline bool dtype_has_tables(int32_t dtype) { return dtype == BS_F32 || dtype == BS_BF16; }
 // Column-block width (elements per lane and row) of the one- / two-level sliding-window kernels.
 inline int32_t rows_vec(int32_t dtype) { return dtype == BS_F32 ? 4 : K_ROWS_VEC16; }
-inline int32_t rows2_vec(int32_t dtype) { return dtype == BS_F32 ? 4 : K_ROWS2_VEC16; }
+inline int32_t rows2_vec(int32_t dtype) { return dtype == BS_F32 ? K_ROWS2_VEC32 : K_ROWS2_VEC16; }
 
 // planner (host only)
 bs_status build_operations(bs_stack *s);

@@ -52,6 +52,7 @@ constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
 // lanes) are 15..30 % slower for the one-level kernel.
 constexpr int K_ROWS_VEC16 = 8;
 constexpr int K_ROWS2_VEC16 = 8;
+constexpr int K_ROWS2_VEC32 = 4;  // float32 in the two-level kernel (8, two loads per row, measured 5 % slower: registers)
 constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
 

@@ -85,7 +85,7 @@ bs_status launch_rows2(const PoolRows2K &k, int32_t dtype, int64_t grid_n, int32
     const bool want_idx = k.idx != nullptr && k.pool2.kind == OP_MAXPOOL;
     if (!dtype_has_tables(dtype)) return BS_ERR_UNSUPPORTED;
     const bool ok = dtype == BS_BF16 ? rows2_launch_t<DT_BF16, K_ROWS2_VEC16>(k, want_idx, grid, block, st)
-                                     : rows2_launch_t<DT_F32, 4>(k, want_idx, grid, block, st);
+                                     : rows2_launch_t<DT_F32, K_ROWS2_VEC32>(k, want_idx, grid, block, st);
     return ok ? BS_OK : BS_ERR_UNSUPPORTED;
 }
 

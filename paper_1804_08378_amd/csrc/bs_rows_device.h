@@ -341,6 +341,9 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     constexpr int R0 = (KH2 - 1) * SH1 + KH1;     // level-0 rows under one output row
     constexpr int NS0 = SH1 * SH2;                // new level-0 rows per output row
     constexpr int ES = DT != DT_F32 ? 2 : 4;
+    constexpr int VPC = 16 / ES;                  // elements per 128-bit load
+    constexpr int NV = VEC / VPC;                 // 128-bit loads per lane and row
+    static_assert(VEC % VPC == 0, "a column block is a whole number of 128-bit vectors");
     constexpr bool MAX1 = P1::kind == OP_MAXPOOL, MAX2 = P2::kind == OP_MAXPOOL;
     static_assert(VEC % (SW1 * SW2) == 0 && NX >= 0 && KEEP0 >= 0 && KEEP1 >= 0, "unsupported pooling shapes");
     using E0 = RowsEw<EW0>;
@@ -378,7 +381,7 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     for (int n = 0; n < NC1; ++n) c1in[n] = c1s + n >= 0 && c1s + n < k.W1;
 
     struct RowRaw {
-        Raw<DT, VEC> v;
+        Raw<DT, VPC> v[NV];
         Raw<DT, 1> l[NL > 0 ? NL : 1], x[NX > 0 ? NX : 1];
         bool ok;
     };
@@ -386,7 +389,8 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     auto fetch = [&](int32_t ih, RowRaw &r) {
         r.ok = ih >= 0 && ih < k.H;
         const uint32_t rowoff = r.ok ? (uint32_t)(ih * k.W) : 0u;
-        r.v = load_raw<DT, VEC>(inp, rowoff + (uint32_t)col0);
+#pragma unroll
+        for (int p = 0; p < NV; ++p) r.v[p] = load_raw<DT, VPC>(inp, rowoff + (uint32_t)(col0 + p * VPC));
 #pragma unroll
         for (int n = 0; n < NL; ++n) r.l[n] = load_raw<DT, 1>(inp, lin[n] ? rowoff + (uint32_t)(col0 - NL + n) : 0u);
 #pragma unroll
@@ -394,10 +398,13 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     };
     // registers -> level-0 row: leading element-wise operations, then the first pool's padding
     auto settle = [&](const RowRaw &r, float (&w)[NC0]) {
-        float xv[VEC];
-        unpack<DT, VEC>(r.v, xv);
 #pragma unroll
-        for (int n = 0; n < VEC; ++n) w[NL + n] = xv[n];
+        for (int p = 0; p < NV; ++p) {
+            float xv[VPC];
+            unpack<DT, VPC>(r.v[p], xv);
+#pragma unroll
+            for (int n = 0; n < VPC; ++n) w[NL + p * VPC + n] = xv[n];
+        }
 #pragma unroll
         for (int n = 0; n < NL; ++n) {
             float one[1];
