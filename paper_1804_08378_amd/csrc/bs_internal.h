@@ -135,6 +135,10 @@ bool lds_precompiled(const LdsSeqK &k, int32_t dtype);
 bool lds_buildable(const LdsSeqK &k);
 std::string lds_expr(const LdsSeqK &k, int32_t dtype, bool want_idx);
 bs_status launch_lds(const LdsSeqK &k, int32_t dtype, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
+// bs_trace.cpp
+bool trace_enabled();
+void trace_push_sequence(const Sequence &q, size_t index, size_t count);
+void trace_pop();
 // bs_jit.cpp
 bool jit_enabled();
 std::string jit_last_log();

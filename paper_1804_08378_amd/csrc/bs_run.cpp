@@ -49,6 +49,7 @@ extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const v
         return BS_ERR_ALIAS;
 
     const size_t n = stack->seqs.size();
+    const bool traced = trace_enabled();
     const void *cur_in = in;
     for (size_t i = 0; i < n; ++i) {
         void *cur_out = out;
@@ -56,7 +57,9 @@ extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const v
             char *half = static_cast<char *>(workspace) + ((i & 1) ? stack->ws_half_bytes : 0);
             cur_out = half;
         }
+        if (traced) trace_push_sequence(stack->seqs[i], i, n);
         bs_status st = launch_sequence(stack, stack->seqs[i], cur_in, cur_out, residuals, indices, stream);
+        if (traced) trace_pop();
         if (st != BS_OK) return st;
         cur_in = cur_out;
     }

@@ -412,6 +412,34 @@ def test_random_stacks_match_the_oracle(seed):
     assert done >= 7
 
 
+# ------------------------------------------------------------------ tracing
+def test_tracing_ranges_do_not_change_results():
+    """BS_TRACE=1 wraps every sequence launch in a rocTX range (looked up at run time); a traced
+    run in a fresh process gives the oracle's result."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import numpy as np, torch\n"
+        "from oracle import breadth_first as bf\n"
+        "from paper_1804_08378_amd import brainslug as bs, workloads as wl\n"
+        "layers = [wl.bn_params(4, 1), wl.relu(), wl.maxpool(3, 2, 1, True), wl.maxpool(3, 1, 1), wl.bn_params(4, 2),\n"
+        "          wl.relu(), wl.avgpool(5, 1, 2), wl.relu()]\n"
+        "x = wl.activation((2, 4, 24, 32), 3)\n"
+        "st = bs.Stack(layers, x.shape, 'f32').plan(max_steps_per_sequence=1)\n"
+        "assert st.info()['n_sequences'] == 3\n"
+        "out, idx = st.run(torch.from_numpy(x).cuda())\n"
+        "torch.cuda.synchronize()\n"
+        "ref, ridx, _ = bf.run_stack(layers, x)\n"
+        "assert np.array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))\n"
+        "assert np.array_equal(idx[0].cpu().numpy(), ridx[0])\n"
+        "print('traced run ok')\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, BS_TRACE="1", PYTHONPATH=root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, cwd=root, timeout=300)
+    assert r.returncode == 0 and "traced run ok" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
+
+
 # ------------------------------------------------------------------ HIP graph capture
 def test_run_can_be_captured_in_a_hip_graph_and_replayed():
     """bs_stack_run only enqueues kernels on the caller's stream (no allocation, no

@@ -39,7 +39,7 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
         assert p.returncode == 0, out.decode()
     lib = str(tmp_path / "libbs_san.so")
     subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-sanitize", *SAN, *objs, *kernel_objs,
-                    "-lhiprtc", "-o", lib], check=True, capture_output=True)
+                    "-lhiprtc", "-ldl", "-o", lib], check=True, capture_output=True)
     exe = str(tmp_path / "host_driver")
     subprocess.run([CLANG, "-O1", "-g", "-std=c++17", *SAN, *inc, os.path.join(HERE, "sanitize", "host_driver.cpp"),
                     "-L", str(tmp_path), "-lbs_san", "-Wl,-rpath," + str(tmp_path), "-o", exe], check=True,
