@@ -15,6 +15,7 @@
  *     bs_stack_plan     layers -> operations -> steps -> sequences -> tiles;
  *                       uploads the folded BatchNorm parameters
  *     bs_stack_run      enqueue the sequence kernels on a HIP stream
+ *                       (bs_stack_run_strided: on channel slices of larger tensors)
  *     bs_stack_destroy
  *
  * Conventions
@@ -275,6 +276,40 @@ BS_API uint64_t bs_stack_workspace_bytes(const bs_stack *stack);
 BS_API bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,
                               void *out, int32_t *const *indices, void *workspace,
                               uint64_t workspace_bytes, void *stream);
+
+/*
+ * bs_stack_run for an input and / or an output that is a channel slice of a larger NCHW
+ * tensor, read and written in place: what a DenseNet-style concatenation buffer needs
+ * (Section 5, DenseNet-121: every dense layer's BatchNorm -> ReLU reads the first channels
+ * of the block's buffer; the stem's pooling writes into it), so that the stack still moves
+ * the tensor through main memory once (Section 3) with no gather / scatter copy around it.
+ *   in, out            device pointers to the first element of the slice (image 0, channel 0
+ *                      of the stack's own C channels)
+ *   in_batch_stride    elements between the starts of consecutive images of the input:
+ *   out_batch_stride   0 = dense (C*H*W of that tensor), else >= C*H*W; the stride times the
+ *                      element size must be a multiple of 16 bytes (BS_ERR_ALIGN)
+ * Channels, rows and columns of a slice stay dense (a slice along the channel axis).
+ * Residual operands, index outputs and the workspace are dense, as in bs_stack_run.
+ * `out` must not overlap an input; two slices of one buffer with the same batch stride count
+ * as disjoint when their per-image byte ranges are.  In place (out == in, equal strides) is
+ * allowed for a stack without pooling layers.
+ * Errors: those of bs_stack_run; BS_ERR_SHAPE for a stride below C*H*W or above 2^31 - 1.
+ */
+BS_API bs_status bs_stack_run_strided(const bs_stack *stack, const void *in, int64_t in_batch_stride,
+                                      const void *const *residuals, void *out,
+                                      int64_t out_batch_stride, int32_t *const *indices,
+                                      void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
+ * The argument checks of bs_stack_run_strided alone: nothing is enqueued, no device is touched
+ * and no pointer is dereferenced (addresses are only compared), so it also works on a
+ * host-only plan.  Returns what bs_stack_run_strided would return for these arguments before
+ * its first launch, device checks (BS_ERR_DEVICE) aside.
+ */
+BS_API bs_status bs_stack_check_buffers(const bs_stack *stack, const void *in, int64_t in_batch_stride,
+                                        const void *const *residuals, const void *out,
+                                        int64_t out_batch_stride, int32_t *const *indices,
+                                        const void *workspace, uint64_t workspace_bytes);
 
 /*
  * Compile, without loading them and without touching any device, all run-time builds the

@@ -93,6 +93,10 @@ _SIGNATURES = {
     "bs_stack_workspace_bytes": (C.c_uint64, [C.c_void_p]),
     "bs_stack_run": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
                                C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_stack_run_strided": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.c_void_p,
+                                       C.c_int64, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_stack_check_buffers": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.c_void_p,
+                                         C.c_int64, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64]),
     "bs_stack_jit_check": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]),
     "bs_jit_log": (C.c_char_p, []),
     "bs_status_string": (C.c_char_p, [C.c_int]),
@@ -318,6 +322,46 @@ def bs_stack_run(handle, in_ptr, residual_ptrs, out_ptr, index_ptrs, workspace_p
                                int(workspace_bytes), C.c_void_p(stream or None)), "bs_stack_run")
 
 
+def bs_stack_run_strided(handle, in_ptr, in_batch_stride, residual_ptrs, out_ptr, out_batch_stride,
+                         index_ptrs, workspace_ptr, workspace_bytes, stream) -> None:
+    """bs_stack_run on channel slices: batch strides in elements (0 = dense)."""
+    res = None
+    if residual_ptrs:
+        res = (C.c_void_p * len(residual_ptrs))(*[C.c_void_p(p or None) for p in residual_ptrs])
+    idx = None
+    if index_ptrs:
+        idx = (C.c_void_p * len(index_ptrs))(*[C.c_void_p(p or None) for p in index_ptrs])
+    _check(load().bs_stack_run_strided(C.c_void_p(handle), C.c_void_p(in_ptr or None), int(in_batch_stride),
+                                       res, C.c_void_p(out_ptr or None), int(out_batch_stride), idx,
+                                       C.c_void_p(workspace_ptr or None), int(workspace_bytes),
+                                       C.c_void_p(stream or None)), "bs_stack_run_strided")
+
+
+def bs_stack_check_buffers(handle, in_ptr, in_batch_stride, residual_ptrs, out_ptr, out_batch_stride,
+                           index_ptrs, workspace_ptr, workspace_bytes) -> int:
+    """The bs_status bs_stack_run_strided's argument checks give (no launch, no device); returned,
+    not raised."""
+    res = None
+    if residual_ptrs:
+        res = (C.c_void_p * len(residual_ptrs))(*[C.c_void_p(p or None) for p in residual_ptrs])
+    idx = None
+    if index_ptrs:
+        idx = (C.c_void_p * len(index_ptrs))(*[C.c_void_p(p or None) for p in index_ptrs])
+    return int(load().bs_stack_check_buffers(C.c_void_p(handle), C.c_void_p(in_ptr or None), int(in_batch_stride),
+                                             res, C.c_void_p(out_ptr or None), int(out_batch_stride), idx,
+                                             C.c_void_p(workspace_ptr or None), int(workspace_bytes)))
+
+
+def batch_stride(t):
+    """Batch stride (elements) of a 4-D tensor that is dense in C, H, W -- a contiguous tensor
+    or a slice of one along the channel axis -- else None."""
+    n, c, h, w = t.shape
+    sn, sc, sh, sw = t.stride()
+    if (w == 1 or sw == 1) and (h == 1 or sh == w) and (c == 1 or sc == h * w) and (n == 1 or sn >= c * h * w):
+        return int(sn) if n > 1 else c * h * w
+    return None
+
+
 # ---- convenience wrapper -----------------------------------------------------------------
 class Stack:
     """A planned stack bound to torch tensors (device memory and streams only)."""
@@ -371,10 +415,13 @@ class Stack:
         return self._workspace if n else None
 
     def run(self, x, residuals=(), out=None, indices=None, stream=None):
-        """Enqueue on `stream` (default: torch's current stream); returns (out, indices)."""
+        """Enqueue on `stream` (default: torch's current stream); returns (out, indices).
+        `x` and `out` may be channel slices (t[:, a:b]) of larger contiguous tensors: they are
+        read and written in place."""
         import torch
-        if tuple(x.shape) != self.in_shape or x.dtype != self.torch_dtype() or not x.is_contiguous():
-            raise ValueError("input must be a contiguous tensor of the stack's shape and dtype")
+        if tuple(x.shape) != self.in_shape or x.dtype != self.torch_dtype() or batch_stride(x) is None:
+            raise ValueError("input must be a tensor of the stack's shape and dtype, contiguous or a "
+                             "channel slice of a contiguous tensor")
         for r in residuals:
             if r.dtype != self.torch_dtype() or not r.is_contiguous():
                 raise ValueError("residuals must be contiguous tensors of the stack's dtype")
@@ -382,9 +429,17 @@ class Stack:
             o2, i2 = self.alloc_outputs(x.device, indices is None)
             out = o2 if out is None else out
             indices = i2 if indices is None else indices
+        if tuple(out.shape) != self.out_shape or out.dtype != self.torch_dtype() or batch_stride(out) is None:
+            raise ValueError("out must be a tensor of the stack's output shape and dtype, contiguous or a "
+                             "channel slice of a contiguous tensor")
         ws = self.workspace(x.device)
         st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
-        bs_stack_run(self.handle, x.data_ptr(), [r.data_ptr() for r in residuals], out.data_ptr(),
-                     [t.data_ptr() if t is not None else 0 for t in indices] if indices else None,
-                     ws.data_ptr() if ws is not None else 0, ws.numel() if ws is not None else 0, st)
+        res = [r.data_ptr() for r in residuals]
+        idx = [t.data_ptr() if t is not None else 0 for t in indices] if indices else None
+        wsp, wsn = (ws.data_ptr(), ws.numel()) if ws is not None else (0, 0)
+        if x.is_contiguous() and out.is_contiguous():
+            bs_stack_run(self.handle, x.data_ptr(), res, out.data_ptr(), idx, wsp, wsn, st)
+        else:
+            bs_stack_run_strided(self.handle, x.data_ptr(), batch_stride(x), res, out.data_ptr(),
+                                 batch_stride(out), idx, wsp, wsn, st)
         return out, indices

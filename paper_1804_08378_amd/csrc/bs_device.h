@@ -65,6 +65,23 @@ BS_DEV float round_store(float v)
     }
 }
 
+// ------------------------------------------------------------ strided images
+// The input and the output of a sequence may be channel slices of larger NCHW tensors: image n
+// then starts `extra` elements later than in a dense tensor for every image before it
+// (extra = batch stride - C*H*W).  All element offsets in the kernels stay those of a dense
+// tensor (they also address residuals and index outputs, which are dense); only the base
+// pointer moves per image.
+template <int DT>
+BS_DEV const void *image_base(const void *p, uint32_t n, uint32_t extra)
+{
+    return static_cast<const char *>(p) + (size_t)n * extra * (DT != DT_F32 ? 2 : 4);
+}
+template <int DT>
+BS_DEV void *image_base(void *p, uint32_t n, uint32_t extra)
+{
+    return static_cast<char *>(p) + (size_t)n * extra * (DT != DT_F32 ? 2 : 4);
+}
+
 // --------------------------------------------------------- vector load/store
 // Raw register block of N consecutive elements (2, 4, 8 or 16 bytes, one load instruction).
 template <int BYTES>

@@ -115,8 +115,11 @@ bs_status device_limits(Limits *lim, int *device);
 int current_device();  // -1 if it cannot be queried
 bs_status upload_params(bs_stack *s);
 void free_params(bs_stack *s);
+// in_extra / out_extra: elements between the end of one image and the start of the next in
+// the sequence's input / output (0 = dense)
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
-                          const void *const *res, int32_t *const *idx, void *stream);
+                          uint32_t in_extra, uint32_t out_extra, const void *const *res,
+                          int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
 // bs_rows.hip: *_supported = the signature is in the pre-compiled table; *_buildable = the
 // kernel template can be instantiated for it at run time; *_expr = that instance's name

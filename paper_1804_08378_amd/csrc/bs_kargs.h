@@ -97,6 +97,7 @@ struct LdsSeqK {
     const void *in;
     void *out;
     const float *params;
+    uint32_t in_extra, out_extra;  // elements to skip per image beyond a dense one: batch stride - C*H*W (0 = dense)
     const void *res[K_MAX_RES];
     int32_t *idx[K_MAX_IDX];
     int32_t n_levels;  // L >= 1 pooling operations; levels 0..L
@@ -114,6 +115,7 @@ struct StreamK {
     const void *in;
     void *out;
     const float *params;
+    uint32_t in_extra, out_extra;  // elements to skip per image beyond a dense one: batch stride - C*H*W (0 = dense)
     const void *res[K_MAX_RES];
     int32_t n_ew;
     EwOp ew[K_MAX_STREAM_EW];
@@ -127,6 +129,7 @@ struct PoolDirectK {
     const void *in;
     void *out;
     const float *params;
+    uint32_t in_extra, out_extra;  // elements to skip per image beyond a dense one: batch stride - C*H*W (0 = dense)
     const void *res[K_MAX_RES];
     int32_t *idx;
     int32_t n_pre, n_post;
@@ -143,6 +146,7 @@ struct PoolRowsK {
     const void *in;
     void *out;
     const float *params;
+    uint32_t in_extra, out_extra;  // elements to skip per image beyond a dense one: batch stride - C*H*W (0 = dense)
     int32_t *idx;
     int32_t n_pre, n_post;
     EwOp pre[K_MAX_EW], post[K_MAX_EW];
@@ -160,6 +164,7 @@ struct PoolRows2K {
     const void *in;
     void *out;
     const float *params;
+    uint32_t in_extra, out_extra;  // elements to skip per image beyond a dense one: batch stride - C*H*W (0 = dense)
     int32_t *idx;     // index output of pool2 (pool1 never has one here)
     int32_t n_pre, n_mid, n_post;
     EwOp pre[K_MAX_EW], mid[K_MAX_EW], post[K_MAX_EW];

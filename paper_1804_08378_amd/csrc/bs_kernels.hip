@@ -101,7 +101,7 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
     Raw<DT, VEC> raw[U];
     bool valid[U];
-    uint32_t off[U];
+    uint32_t off[U], img[U];
     int32_t c[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -109,9 +109,10 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
         valid[u] = i < k.total;
         i = valid[u] ? i : 0u;
         off[u] = i * VEC;
-        raw[u] = load_raw<DT, VEC, true>(k.in, off[u]);
         const uint32_t plane = fdiv(i, k.div_plane);
-        c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+        img[u] = fdiv(plane, k.div_c);
+        c[u] = (int32_t)(plane - img[u] * (uint32_t)k.C);
+        raw[u] = load_raw<DT, VEC, true>(image_base<DT>(k.in, img[u], k.in_extra), off[u]);
     }
     float x[U][VEC];
 #pragma unroll
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
     apply_ew<DT, VEC, U>(x, c, off, k.ew, k.n_ew, k.params, k.C, k.res);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (valid[u]) store_elems<DT, VEC>(k.out, off[u], x[u]);
+        if (valid[u]) store_elems<DT, VEC>(image_base<DT>(k.out, img[u], k.out_extra), off[u], x[u]);
 }
 
 // =============================================================================
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 
     Raw<DT, VEC> raw[U][KH];
     bool valid[U];
-    uint32_t in_off[U], out_off[U], idx0[U];
+    uint32_t in_off[U], out_off[U], idx0[U], img[U];
     int32_t c[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -154,12 +155,14 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
         const uint32_t cv = i - t * wv;
         const uint32_t plane = fdiv(t, k.div_ho);
         const uint32_t oh = t - plane * (uint32_t)k.Ho;
-        c[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+        img[u] = fdiv(plane, k.div_c);
+        c[u] = (int32_t)(plane - img[u] * (uint32_t)k.C);
         idx0[u] = (oh * KH) * (uint32_t)k.W + cv * VEC;  // first cell of the unit in its plane
         in_off[u] = plane * (uint32_t)(k.H * k.W) + idx0[u];
         out_off[u] = (plane * (uint32_t)k.Ho + oh) * (uint32_t)k.Wo + cv * NO;
+        const void *inp = image_base<DT>(k.in, img[u], k.in_extra);
 #pragma unroll
-        for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<DT, VEC, true>(k.in, in_off[u] + dh * (uint32_t)k.W);
+        for (int dh = 0; dh < KH; ++dh) raw[u][dh] = load_raw<DT, VEC, true>(inp, in_off[u] + dh * (uint32_t)k.W);
     }
     float sc[U], sh[U];
     if constexpr (SIG == 1) {
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(512) void pool_direct_kernel(const PoolDirectK k)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (!valid[u]) continue;
-        store_elems<DT, NO>(k.out, out_off[u], y[u]);
+        store_elems<DT, NO>(image_base<DT>(k.out, img[u], k.out_extra), out_off[u], y[u]);
         if (want_idx && is_max) {
             store_indices<NO>(k.idx + out_off[u], yi[u]);
         }
@@ -265,15 +268,17 @@ __global__ __launch_bounds__(256) void plane_pool_kernel(const PoolDirectK k)
     uint32_t plane = blockIdx.x * blockDim.x + threadIdx.x;
     const bool live = plane < k.total;
     plane = live ? plane : 0u;
-    const int32_t c1[1] = {(int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C)};
+    const uint32_t img = fdiv(plane, k.div_c);
+    const int32_t c1[1] = {(int32_t)(plane - img * (uint32_t)k.C)};
     const uint32_t hw = (uint32_t)(k.H * k.W), base = plane * hw;
+    const void *inp = image_base<DT>(k.in, img, k.in_extra);
     const bool is_max = k.pool.kind == OP_MAXPOOL;
     float acc = is_max ? -INFINITY : 0.0f;
     int32_t bi = 0;  // first cell of the plane
     for (uint32_t i0 = 0; i0 < hw; i0 += U) {
         Raw<DT, 1> raw[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) raw[u] = load_raw<DT, 1>(k.in, base + min(i0 + u, hw - 1));
+        for (int u = 0; u < U; ++u) raw[u] = load_raw<DT, 1>(inp, base + min(i0 + u, hw - 1));
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             float x[1][1];
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(256) void plane_pool_kernel(const PoolDirectK k)
     const uint32_t oo[1] = {plane};  // Ho = Wo = 1: the output (and a residual of its shape) is indexed by plane
     apply_ew<DT, 1, 1>(y, c1, oo, k.post, k.n_post, k.params, k.C, k.res);
     if (live) {
-        store_elems<DT, 1>(k.out, plane, y[0]);
+        store_elems<DT, 1>(image_base<DT>(k.out, img, k.out_extra), plane, y[0]);
         if (k.idx && is_max) k.idx[plane] = bi;
     }
 }
@@ -399,7 +404,8 @@ static bs_status launch_built(const Sequence &q, bool want_idx, const void *args
 }
 
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
-                          const void *const *res, int32_t *const *idx, void *stream)
+                          uint32_t in_extra, uint32_t out_extra, const void *const *res,
+                          int32_t *const *idx, void *stream)
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t dtype = s->dtype;
@@ -416,6 +422,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         if (q.vec != 1 && q.vec != (dtype == BS_F32 ? 4 : 8)) return BS_ERR_UNSUPPORTED;
         StreamK k = q.stream;
         k.in = in; k.out = out; k.params = s->dev_params;
+        k.in_extra = in_extra; k.out_extra = out_extra;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         if (dtype == BS_BF16) {
             if (q.vec == 8) stream_kernel<DT_BF16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
@@ -433,6 +440,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         if (q.vec != (dtype == BS_F32 ? 4 : 8) || (int64_t)q.direct.div_wv.d * q.vec != q.direct.W) return BS_ERR_UNSUPPORTED;
         PoolDirectK k = q.direct;
         k.in = in; k.out = out; k.params = s->dev_params;
+        k.in_extra = in_extra; k.out_extra = out_extra;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];
         if (dtype == BS_BF16) launch_direct<DT_BF16, 8>(k, grid, block, st);
@@ -443,6 +451,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
     case BS_VARIANT_PLANE_POOL: {
         PoolDirectK k = q.direct;
         k.in = in; k.out = out; k.params = s->dev_params;
+        k.in_extra = in_extra; k.out_extra = out_extra;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];
         if (dtype == BS_BF16) plane_pool_kernel<DT_BF16><<<grid, block, 0, st>>>(k);
@@ -454,6 +463,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         if (q.n_levels == 2) {
             PoolRows2K k = q.rows2;
             k.in = in; k.out = out; k.params = s->dev_params;
+            k.in_extra = in_extra; k.out_extra = out_extra;
             k.idx = ip[0];
             const bool want_idx = k.idx != nullptr && k.pool2.kind == OP_MAXPOOL;
             const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
@@ -463,6 +473,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         }
         PoolRowsK k = q.rows;
         k.in = in; k.out = out; k.params = s->dev_params;
+        k.in_extra = in_extra; k.out_extra = out_extra;
         k.idx = ip[0];
         const bool want_idx = k.idx != nullptr && k.pool.kind == OP_MAXPOOL;
         const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
@@ -473,6 +484,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
     case BS_VARIANT_LDS_TILE: {
         LdsSeqK k = q.lds;
         k.in = in; k.out = out; k.params = s->dev_params;
+        k.in_extra = in_extra; k.out_extra = out_extra;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         for (int j = 0; j < K_MAX_IDX; ++j) k.idx[j] = ip[j];
         bool want_idx = false;

@@ -411,7 +411,9 @@ BS_DEV void phase0(const LdsSeqK &k, const TileCtx &t, float *lds, int32_t r0, i
     float *dst = lds + lv.buf_off;
     for (int32_t pl = 0; pl < t.nplanes; ++pl) {
         const uint32_t plane = (uint32_t)(t.plane0 + pl);
-        const int32_t ch = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+        const uint32_t img = fdiv(plane, k.div_c);
+        const int32_t ch = (int32_t)(plane - img * (uint32_t)k.C);
+        const void *inp = image_base<DT>(k.in, img, k.in_extra);
         EwRegs<EW> er;
         load_ew_regs<EW>(lv, k.params, k.C, ch, er);
         const uint32_t gplane = plane * (uint32_t)(lv.H * lv.W);
@@ -429,7 +431,7 @@ BS_DEV void phase0(const LdsSeqK &k, const TileCtx &t, float *lds, int32_t r0, i
                     const int32_t gr = r0 + r;
                     inimg[u] = col_in && r < lv.rows && gr >= 0 && gr < lv.H;
                     off[u] = inimg[u] ? gplane + (uint32_t)gr * (uint32_t)lv.W + (uint32_t)gc : 0u;
-                    raw[u] = load_raw<DT, VEC, true>(k.in, off[u]);
+                    raw[u] = load_raw<DT, VEC, true>(inp, off[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -485,7 +487,9 @@ BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, con
     const int32_t spr = lv.items_per_row;
     for (int32_t pl = 0; pl < t.nplanes; ++pl) {
         const uint32_t plane = (uint32_t)(t.plane0 + pl);
-        const int32_t ch = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+        const uint32_t img = fdiv(plane, k.div_c);
+        const int32_t ch = (int32_t)(plane - img * (uint32_t)k.C);
+        void *outp = LAST ? image_base<DT>(k.out, img, k.out_extra) : nullptr;
         EwRegs<EW> er;
         load_ew_regs<EW>(lv, k.params, k.C, ch, er);
         const float *splane = cx.src + pl * pv.plane_stride;
@@ -527,13 +531,13 @@ BS_DEV void pool_phase(const LdsSeqK &k, const TileCtx &t, const LevelK &lv, con
                 if (LAST) {
                     if (row_in && gr < cx.end_r) {
                         if (strip_vec) {
-                            store_elems<DT, VO>(k.out, goff + (uint32_t)gc, val);
+                            store_elems<DT, VO>(outp, goff + (uint32_t)gc, val);
                         } else {
 #pragma unroll
                             for (int e = 0; e < VO; ++e)
                                 if (cin[e] && gc + e < cx.end_c) {
                                     const float one[1] = {val[e]};
-                                    store_elems<DT, 1>(k.out, goff + (uint32_t)(gc + e), one);
+                                    store_elems<DT, 1>(outp, goff + (uint32_t)(gc + e), one);
                                 }
                         }
                     }

@@ -147,14 +147,17 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
     const int32_t j = (int32_t)(i - t * (uint32_t)k.cbs);
     const uint32_t plane = fdiv(t, k.div_chunks);
     const int32_t chunk = (int32_t)(t - plane * (uint32_t)k.chunks);
-    const int32_t c = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+    const uint32_t img = fdiv(plane, k.div_c);
+    const int32_t c = (int32_t)(plane - img * (uint32_t)k.C);
 
     RowsParams<EWP> pp;
     RowsParams<EWQ> qp;
     rows_load_params<EWP>(k.pre, k.params, k.C, c, pp);
     rows_load_params<EWQ>(k.post, k.params, k.C, c, qp);
 
-    const char *inp = static_cast<const char *>(k.in) + (size_t)plane * (size_t)(k.H * k.W) * ES;
+    const char *inp = static_cast<const char *>(image_base<DT>(k.in, img, k.in_extra)) +
+                      (size_t)plane * (size_t)(k.H * k.W) * ES;
+    void *outp = image_base<DT>(k.out, img, k.out_extra);
     const int32_t col0 = j * VEC;  // first column of the lane's block
     bool lin[NL > 0 ? NL : 1], xin[NX > 0 ? NX : 1];
 #pragma unroll
@@ -279,7 +282,7 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
             if (oh + o < oh1) {
                 const uint32_t ooff = oplane + (uint32_t)((oh + o) * k.Wo + ow0);
                 if (vec_store) {
-                    store_elems<DT, VO>(k.out, ooff, y);
+                    store_elems<DT, VO>(outp, ooff, y);
                     if constexpr (WANT_IDX) {
                         if (k.idx) store_indices<VO>(k.idx + ooff, yi);
                     }
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(256) void pool_rows_kernel(const PoolRowsK k)
                     for (int e = 0; e < VO; ++e)
                         if (ow0 + e < k.Wo) {
                             const float one[1] = {y[e]};
-                            store_elems<DT, 1>(k.out, ooff + e, one);
+                            store_elems<DT, 1>(outp, ooff + e, one);
                             if constexpr (WANT_IDX) {
                                 if (k.idx) k.idx[ooff + e] = yi[e];
                             }
@@ -360,7 +363,8 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     const int32_t j = (int32_t)(i - t * (uint32_t)k.cbs);
     const uint32_t plane = fdiv(t, k.div_chunks);
     const int32_t chunk = (int32_t)(t - plane * (uint32_t)k.chunks);
-    const int32_t c = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+    const uint32_t img = fdiv(plane, k.div_c);
+    const int32_t c = (int32_t)(plane - img * (uint32_t)k.C);
 
     RowsParams<E0> p0;
     RowsParams<E1> p1;
@@ -369,7 +373,9 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
     rows_load_params<E1>(k.mid, k.params, k.C, c, p1);
     rows_load_params<E2>(k.post, k.params, k.C, c, p2);
 
-    const char *inp = static_cast<const char *>(k.in) + (size_t)plane * (size_t)(k.H * k.W) * ES;
+    const char *inp = static_cast<const char *>(image_base<DT>(k.in, img, k.in_extra)) +
+                      (size_t)plane * (size_t)(k.H * k.W) * ES;
+    void *outp = image_base<DT>(k.out, img, k.out_extra);
     const int32_t col0 = j * VEC;            // first level-0 column of the lane's block
     const int32_t c1s = j * VB - PW2;        // first level-1 column the lane computes
     bool lin[NL > 0 ? NL : 1], xin[NX > 0 ? NX : 1], c1in[NC1];
@@ -540,7 +546,7 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
         {
             const uint32_t ooff = oplane + (uint32_t)(oh * k.Wo + ow0);
             if (vec_store) {
-                store_elems<DT, VO, false>(k.out, ooff, y);
+                store_elems<DT, VO, false>(outp, ooff, y);
                 if constexpr (WANT_IDX) {
                     if (k.idx) store_indices<VO>(k.idx + ooff, yi);
                 }
@@ -549,7 +555,7 @@ __global__ __launch_bounds__(256) void pool_rows2_kernel(const PoolRows2K k)
                 for (int e = 0; e < VO; ++e)
                     if (ow0 + e < k.Wo) {
                         const float one[1] = {y[e]};
-                        store_elems<DT, 1, false>(k.out, ooff + e, one);
+                        store_elems<DT, 1, false>(outp, ooff + e, one);
                         if constexpr (WANT_IDX) {
                             if (k.idx) k.idx[ooff + e] = yi[e];
                         }

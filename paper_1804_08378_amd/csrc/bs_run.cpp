@@ -8,27 +8,64 @@
 
 using namespace bs;
 
-static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+namespace {
 
-static inline bool overlap(const void *a, uint64_t na, const void *b, uint64_t nb)
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline bool overlap(const void *a, uint64_t na, const void *b, uint64_t nb)
 {
     const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
     return x < y + nb && y < x + na;
 }
 
-static inline uint64_t numel(const int64_t *sh) { return (uint64_t)sh[0] * sh[1] * sh[2] * sh[3]; }
+inline uint64_t numel(const int64_t *sh) { return (uint64_t)sh[0] * sh[1] * sh[2] * sh[3]; }
 
-extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,
-                                  void *out, int32_t *const *indices, void *workspace,
-                                  uint64_t workspace_bytes, void *stream)
+// A tensor of `images` images of `image_bytes` each, consecutive images `stride_bytes` apart.
+struct Span {
+    const void *p;
+    uint64_t images, image_bytes, stride_bytes;
+    uint64_t extent() const { return (images - 1) * stride_bytes + image_bytes; }
+    bool dense() const { return stride_bytes == image_bytes; }
+};
+
+// Do the two tensors share a byte?  Exact for dense tensors; for strided ones it may say yes
+// for disjoint layouts it cannot prove disjoint (never no for overlapping ones).
+bool spans_overlap(const Span &a, const Span &b)
 {
-    if (!stack || !in || !out) return BS_ERR_NULL;
-    if (!stack->planned || !stack->device_planned) return BS_ERR_NOT_PLANNED;
-    if (current_device() != stack->device) return BS_ERR_DEVICE;
+    if (!overlap(a.p, a.extent(), b.p, b.extent())) return false;
+    if (a.dense() && b.dense()) return true;
+    if (a.stride_bytes != b.stride_bytes) return true;
+    // Same stride S: image i of a covers [pa + i*S, +la), image j of b covers [pb + j*S, +lb).
+    // With d = (pb - pa) mod S they are disjoint for all i, j when la <= d and d + lb <= S.
+    const uint64_t S = a.stride_bytes;
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(a.p), pb = reinterpret_cast<uintptr_t>(b.p);
+    const uint64_t d = pb >= pa ? (pb - pa) % S : (S - (pa - pb) % S) % S;
+    return !(a.image_bytes <= d && d + b.image_bytes <= S);
+}
+
+// Everything bs_stack_run checks about its pointer arguments; compares addresses only.  On
+// success the batch strides are resolved (0 -> dense).
+bs_status check_buffers(const bs_stack *stack, const void *in, int64_t &in_stride,
+                        const void *const *residuals, const void *out, int64_t &out_stride,
+                        int32_t *const *indices, const void *workspace, uint64_t workspace_bytes)
+{
     if (stack->n_res > 0 && !residuals) return BS_ERR_NULL;
     for (int32_t i = 0; i < stack->n_res; ++i)
         if (!residuals[i]) return BS_ERR_NULL;
+
+    const uint64_t es = dtype_size(stack->dtype);
+    const uint64_t images = (uint64_t)stack->in_shape[0];
+    const uint64_t in_image = numel(stack->in_shape) / images, out_image = numel(stack->out_shape) / images;
+    if (in_stride == 0) in_stride = (int64_t)in_image;
+    if (out_stride == 0) out_stride = (int64_t)out_image;
+    if (in_stride < (int64_t)in_image || out_stride < (int64_t)out_image) return BS_ERR_SHAPE;
+    if (in_stride > 0x7fffffffll || out_stride > 0x7fffffffll) return BS_ERR_SHAPE;
+    const Span sin{in, images, in_image * es, (uint64_t)in_stride * es};
+    const Span sout{out, images, out_image * es, (uint64_t)out_stride * es};
+
     if (!aligned16(in) || !aligned16(out)) return BS_ERR_ALIGN;
+    if (sin.stride_bytes % 16 != 0 && !sin.dense()) return BS_ERR_ALIGN;
+    if (sout.stride_bytes % 16 != 0 && !sout.dense()) return BS_ERR_ALIGN;
     for (int32_t i = 0; i < stack->n_res; ++i)
         if (!aligned16(residuals[i])) return BS_ERR_ALIGN;
     if (indices)
@@ -38,15 +75,33 @@ extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const v
         if (!workspace || workspace_bytes < stack->workspace_bytes) return BS_ERR_WORKSPACE;
         if (!aligned16(workspace)) return BS_ERR_ALIGN;
     }
-    const uint64_t es = dtype_size(stack->dtype);
-    const uint64_t in_bytes = numel(stack->in_shape) * es, out_bytes = numel(stack->out_shape) * es;
-    if (overlap(in, in_bytes, out, out_bytes) && !(in == out && !stack->has_pool)) return BS_ERR_ALIAS;
-    for (int32_t i = 0; i < stack->n_res; ++i)
-        if (overlap(residuals[i], numel(stack->res_shape[i]) * es, out, out_bytes)) return BS_ERR_ALIAS;
-    if (stack->workspace_bytes > 0 &&
-        (overlap(workspace, stack->workspace_bytes, out, out_bytes) ||
-         overlap(workspace, stack->workspace_bytes, in, in_bytes)))
-        return BS_ERR_ALIAS;
+
+    const bool in_place = in == out && sin.stride_bytes == sout.stride_bytes && !stack->has_pool;
+    if (!in_place && spans_overlap(sin, sout)) return BS_ERR_ALIAS;
+    for (int32_t i = 0; i < stack->n_res; ++i) {
+        const uint64_t b = numel(stack->res_shape[i]) * es;
+        if (spans_overlap(Span{residuals[i], 1, b, b}, sout)) return BS_ERR_ALIAS;
+    }
+    if (stack->workspace_bytes > 0) {
+        const Span ws{workspace, 1, stack->workspace_bytes, stack->workspace_bytes};
+        if (spans_overlap(ws, sout) || spans_overlap(ws, sin)) return BS_ERR_ALIAS;
+    }
+
+    return BS_OK;
+}
+
+bs_status run(const bs_stack *stack, const void *in, int64_t in_stride, const void *const *residuals,
+              void *out, int64_t out_stride, int32_t *const *indices, void *workspace,
+              uint64_t workspace_bytes, void *stream)
+{
+    if (!stack || !in || !out) return BS_ERR_NULL;
+    if (!stack->planned || !stack->device_planned) return BS_ERR_NOT_PLANNED;
+    if (current_device() != stack->device) return BS_ERR_DEVICE;
+    const bs_status cs = check_buffers(stack, in, in_stride, residuals, out, out_stride, indices, workspace,
+                                       workspace_bytes);
+    if (cs != BS_OK) return cs;
+    const uint64_t images = (uint64_t)stack->in_shape[0];
+    const uint64_t in_image = numel(stack->in_shape) / images, out_image = numel(stack->out_shape) / images;
 
     const size_t n = stack->seqs.size();
     const bool traced = trace_enabled();
@@ -57,11 +112,44 @@ extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const v
             char *half = static_cast<char *>(workspace) + ((i & 1) ? stack->ws_half_bytes : 0);
             cur_out = half;
         }
+        // only the stack's own input and output can be slices; the workspace halves are dense
+        const uint32_t in_extra = i == 0 ? (uint32_t)((uint64_t)in_stride - in_image) : 0u;
+        const uint32_t out_extra = i + 1 == n ? (uint32_t)((uint64_t)out_stride - out_image) : 0u;
         if (traced) trace_push_sequence(stack->seqs[i], i, n);
-        bs_status st = launch_sequence(stack, stack->seqs[i], cur_in, cur_out, residuals, indices, stream);
+        bs_status st = launch_sequence(stack, stack->seqs[i], cur_in, cur_out, in_extra, out_extra,
+                                       residuals, indices, stream);
         if (traced) trace_pop();
         if (st != BS_OK) return st;
         cur_in = cur_out;
     }
     return BS_OK;
+}
+
+}  // namespace
+
+extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,
+                                  void *out, int32_t *const *indices, void *workspace,
+                                  uint64_t workspace_bytes, void *stream)
+{
+    return run(stack, in, 0, residuals, out, 0, indices, workspace, workspace_bytes, stream);
+}
+
+extern "C" bs_status bs_stack_run_strided(const bs_stack *stack, const void *in, int64_t in_batch_stride,
+                                          const void *const *residuals, void *out,
+                                          int64_t out_batch_stride, int32_t *const *indices,
+                                          void *workspace, uint64_t workspace_bytes, void *stream)
+{
+    return run(stack, in, in_batch_stride, residuals, out, out_batch_stride, indices, workspace,
+               workspace_bytes, stream);
+}
+
+extern "C" bs_status bs_stack_check_buffers(const bs_stack *stack, const void *in, int64_t in_batch_stride,
+                                            const void *const *residuals, const void *out,
+                                            int64_t out_batch_stride, int32_t *const *indices,
+                                            const void *workspace, uint64_t workspace_bytes)
+{
+    if (!stack || !in || !out) return BS_ERR_NULL;
+    if (!stack->planned) return BS_ERR_NOT_PLANNED;
+    return check_buffers(stack, in, in_batch_stride, residuals, out, out_batch_stride, indices, workspace,
+                         workspace_bytes);
 }

@@ -159,7 +159,10 @@ class BrainSlugStack(nn.Module):
             raise RuntimeError(f"expected {self.channels} channels, got {x.shape[1]}")
         with torch.no_grad():
             st = self.plan_for(x.shape, x.dtype)
-            out, _ = st.run(x.contiguous(), indices=[])
+            # a channel slice of a concatenation buffer is read in place; other layouts are copied
+            if bs.batch_stride(x) is None or (x.data_ptr() % 16) or (x.stride(0) * x.element_size()) % 16:
+                x = x.contiguous()
+            out, _ = st.run(x, indices=[])
         return out
 
     def close(self) -> None:

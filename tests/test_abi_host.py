@@ -136,6 +136,80 @@ def test_plan_option_validation():
         bs.bs_stack_destroy(h)
 
 
+def test_buffer_checks_against_brute_force_byte_sets():
+    """The argument checks of the strided run (host only, fake addresses): an overlap of the
+    output with an input is never let through, slices of one buffer that interleave without
+    sharing a byte are accepted, and stride / alignment errors have their own codes.  The
+    expected answers come from explicit byte sets, not from the library's interval logic."""
+    n, c, h, w = 3, 2, 8, 8
+    layers = [wl.relu(), wl.maxpool(2, 2), wl.add(), wl.avgpool(2, 2)]
+    hd = bs.bs_stack_create(layers, (n, c, h, w), "f32")
+    try:
+        bs.bs_stack_plan(hd, host_only=1, max_steps_per_sequence=1)  # several sequences: needs a workspace
+        wsn = bs.bs_stack_workspace_bytes(hd)
+        assert wsn > 0
+        in_img, out_img = c * h * w * 4, c * (h // 4) * (w // 4) * 4
+        res_bytes = n * c * (h // 2) * (w // 2) * 4
+
+        def bytes_of(p, img, stride_b):
+            return {p + i * stride_b + b for i in range(n) for b in range(img)}
+
+        far_res, far_ws = 1 << 30, 1 << 31
+        rng = np.random.default_rng(5)
+        seen = {0: 0, 12: 0}
+        for _ in range(400):
+            s_in = int(rng.choice([0, 128, 132, 136, 160, 256]))   # elements
+            s_out = int(rng.choice([0, 8, 12, 128, 136, 160, 256]))
+            p_in = 4096
+            p_out = 4096 + 16 * int(rng.integers(-40, 120))
+            st = bs.bs_stack_check_buffers(hd, p_in, s_in, [far_res], p_out, s_out, None, far_ws, wsn)
+            truth = bool(bytes_of(p_in, in_img, (s_in or 128) * 4) & bytes_of(p_out, out_img, (s_out or 8) * 4))
+            assert st in (0, 12), (st, s_in, s_out, p_out)
+            if truth:
+                assert st == 12, (s_in, s_out, p_out)
+            if st == 0:
+                assert not truth
+            # equal strides and disjoint images of one buffer: must be accepted
+            if not truth and (s_in or 128) == (s_out or 8):
+                assert st == 0, (s_in, s_out, p_out)
+            seen[st] += 1
+        assert seen[0] > 20 and seen[12] > 20
+        # interleaved slices of one concatenation buffer (channels [0,2) in, [2,..) out)
+        assert bs.bs_stack_check_buffers(hd, 4096, 256, [far_res], 4096 + in_img, 256, None, far_ws, wsn) == 0
+        # residual or workspace under the output
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, [1 << 20], (1 << 20) + res_bytes - 16, 0, None, far_ws, wsn) == 12
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, [far_res], far_ws + 16, 0, None, far_ws, wsn) == 12
+        assert bs.bs_stack_check_buffers(hd, far_ws + wsn - 16, 0, [far_res], 1 << 20, 0, None, far_ws, wsn) == 12
+        # strides: below the image, not a multiple of 16 bytes, beyond 2^31 - 1 elements
+        assert bs.bs_stack_check_buffers(hd, 4096, 127, [far_res], 1 << 20, 0, None, far_ws, wsn) == 2
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, [far_res], 1 << 20, 7, None, far_ws, wsn) == 2
+        assert bs.bs_stack_check_buffers(hd, 4096, 129, [far_res], 1 << 20, 0, None, far_ws, wsn) == 7
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, [far_res], 1 << 20, 10, None, far_ws, wsn) == 7
+        assert bs.bs_stack_check_buffers(hd, 4096, 1 << 31, [far_res], 1 << 20, 0, None, far_ws, wsn) == 2
+        # pointers: misaligned, missing, workspace too small
+        assert bs.bs_stack_check_buffers(hd, 4100, 0, [far_res], 1 << 20, 0, None, far_ws, wsn) == 7
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, None, 1 << 20, 0, None, far_ws, wsn) == 1
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, [far_res], 1 << 20, 0, None, far_ws, wsn - 1) == 8
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, [far_res], 1 << 20, 0, None, 0, 0) == 8
+    finally:
+        bs.bs_stack_destroy(hd)
+    # in place: allowed without pooling and with equal strides only
+    hd = bs.bs_stack_create([wl.relu()], (n, c, h, w), "f32")
+    try:
+        bs.bs_stack_plan(hd, host_only=1)
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, None, 4096, 0, None, 0, 0) == 0
+        assert bs.bs_stack_check_buffers(hd, 4096, 256, None, 4096, 256, None, 0, 0) == 0
+        assert bs.bs_stack_check_buffers(hd, 4096, 256, None, 4096, 0, None, 0, 0) == 12
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, None, 4096 + 16, 0, None, 0, 0) == 12
+    finally:
+        bs.bs_stack_destroy(hd)
+    hd = bs.bs_stack_create([wl.relu()], (n, c, h, w), "f32")
+    try:
+        assert bs.bs_stack_check_buffers(hd, 4096, 0, None, 1 << 20, 0, None, 0, 0) == 5  # no plan yet
+    finally:
+        bs.bs_stack_destroy(hd)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(bs, "_lib", None)
     monkeypatch.setattr(bs, "LIB_PATH", "/nonexistent/libbrainslug_hip.so")

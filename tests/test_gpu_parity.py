@@ -510,6 +510,117 @@ def test_global_pooling_one_lane_per_plane(shape, dtype):
         check(layers, x, res, dtype, f"global/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
 
 
+# ------------------------------------------------------------------ channel slices
+def _run_sliced(layers, x, res, dtype, lead, trail, **opts):
+    """Run with the input and the output as channel slices [lead, lead + C) of tensors with
+    lead + C + trail channels, read and written in place.  Returns (out, indices, info); checks
+    that no byte of the output tensor outside the slice was written."""
+    n, c, h, w = x.shape
+    st = bs.Stack(layers, x.shape, dtype).plan(**opts)
+    td = TORCH_DTYPE[dtype]
+    big_in = torch.full((n, lead + c + trail, h, w), float("nan"), dtype=td, device="cuda")
+    big_in[:, lead:lead + c] = _dev(x, dtype)
+    oshape = st.out_shape
+    guard = 12345.0
+    big_out = torch.full((n, lead + c + trail) + tuple(oshape[2:]), guard, dtype=td, device="cuda")
+    xs, outs = big_in[:, lead:lead + c], big_out[:, lead:lead + c]
+    assert not xs.is_contiguous() or n == 1
+    out, idx = st.run(xs, [_dev(r, dtype) for r in res], out=outs)
+    torch.cuda.synchronize()
+    assert out.data_ptr() == outs.data_ptr()
+    assert bool((big_out[:, :lead] == guard).all()) and bool((big_out[:, lead + c:] == guard).all()), \
+        "wrote outside the output slice"
+    assert bool(torch.isnan(big_in[:, :lead]).all()) and bool(torch.isnan(big_in[:, lead + c:]).all())
+    info = st.info()
+    o = outs.float().cpu().numpy()
+    ii = [t.cpu().numpy() for t in idx]
+    st.close()
+    return o, ii, info
+
+
+def _check_sliced(layers, x, res, dtype, label, **opts):
+    print(f"[parity] sliced/{label} shape={x.shape} dtype={dtype} opts={opts}", flush=True)
+    ref, ref_idx, _ = bf.run_stack(layers, x, res, dtype)
+    out, idx, info = _run_sliced(layers, x, res, dtype, 8, 8, **opts)
+    ndiff = int((out.view(np.uint32) != ref.view(np.uint32)).sum())
+    print(f"         non-identical={ndiff} "
+          f"variants={[q['variant_name'] + ('*' if q['run_time_build'] else '') for q in info['sequences']]}", flush=True)
+    assert out.shape == ref.shape and ndiff == 0, label
+    assert len(idx) == len(ref_idx)
+    for a, b in zip(idx, ref_idx):
+        assert np.array_equal(a, b), label
+    return info
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 12, 16), (3, 8, 9, 8), (2, 8, 33, 24), (3, 8, 13, 11)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_channel_slices_are_read_and_written_in_place(shape, dtype):
+    """Input and output as channel slices of larger tensors (a concatenation buffer), through
+    every kernel family and through several sequences: results identical to the dense run's
+    oracle, nothing outside the slices touched.  Eight channels on either side of an
+    eight-channel slice keep every image start on a 16-byte boundary for any plane size."""
+    c = shape[1]
+    stacks = {}
+    stacks.update({"s/" + k: (v, None) for k, v in _stacks(c).items()})
+    stacks.update({"r/" + k: (v, None) for k, v in list(_rows_stacks(c).items())[:4]})
+    stacks.update({"r2/" + k: (v, bs.BS_VARIANT_POOL_ROWS) for k, v in _rows2_stacks(c).items()})
+    stacks.update({"b/" + k: (v[0], None) for k, v in _built_stacks(c).items()})
+    h, w = shape[2], shape[3]
+    stacks["g/avg_head"] = ([wl.bn_params(c, 98), wl.relu(), wl.avgpool((h, w), (h, w), 0)], None)
+    stacks["g/max_head"] = ([wl.maxpool((h, w), (1, 1), 0, True), wl.relu()], None)
+    seen = set()
+    for name, (layers, force) in stacks.items():
+        cur, ok = shape, True
+        for l in layers:
+            cur = wl.output_shape([l], cur)
+            ok = ok and cur[2] >= 1 and cur[3] >= 1
+        if not ok:
+            continue
+        x = wl.activation(shape, 90, dtype)
+        res = [wl.activation(sh, 91 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
+        plans = [dict(), dict(max_steps_per_sequence=1), dict(jit=-1)]
+        if force:
+            plans = [dict(force_variant=force)]
+        if any(l["kind"] in ("maxpool", "avgpool") for l in layers) and not force:
+            plans.append(dict(force_variant=bs.BS_VARIANT_LDS_TILE, tile_rows=3, tile_cols=5, planes_per_group=3))
+        for opts in plans:
+            info = _check_sliced(layers, x, res, dtype, f"{name}{shape}", **opts)
+            seen.update(q["variant_name"] for q in info["sequences"])
+    assert {"stream", "lds_tile", "plane_pool"} <= seen
+    if shape[3] % 8 == 0:
+        assert {"pool_direct", "pool_rows"} <= seen
+
+
+def test_channel_slice_in_place_and_argument_errors():
+    layers = [wl.bn_params(8, 3), wl.relu()]
+    x = wl.activation((3, 8, 6, 8), 95)
+    ref, _, _ = bf.run_stack(layers, x, [])
+    st = bs.Stack(layers, x.shape, "f32").plan()
+    big = torch.zeros((3, 24, 6, 8), device="cuda")
+    big[:, 8:16] = _dev(x, "f32")
+    before = big.clone()
+    view = big[:, 8:16]
+    st.run(view, out=view, indices=[])  # in place on a slice
+    torch.cuda.synchronize()
+    assert np.array_equal(view.cpu().numpy(), ref)
+    assert torch.equal(big[:, :8], before[:, :8]) and torch.equal(big[:, 16:], before[:, 16:])
+    # slices of one buffer that interleave without sharing a byte are fine ...
+    big[:, 8:16] = _dev(x, "f32")
+    st.run(big[:, 8:16], out=big[:, 16:24], indices=[])
+    torch.cuda.synchronize()
+    assert np.array_equal(big[:, 16:24].cpu().numpy(), ref)
+    # ... overlapping ones are refused, and so are layouts that are not channel slices
+    with pytest.raises(bs.BrainSlugError) as e:
+        st.run(big[:, 8:16], out=big[:, 12:20], indices=[])
+    assert e.value.status == 12
+    with pytest.raises(ValueError):
+        st.run(torch.zeros((3, 8, 6, 16), device="cuda")[:, :, :, :8], indices=[])
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.bs_stack_run_strided(st.handle, big.data_ptr(), 8 * 6 * 8 - 4, None, view.data_ptr(), 0, None, 0, 0, 0)
+    assert e.value.status == 2
+    st.close()
+
+
 # ------------------------------------------------------------------ further activations
 def _activation_stacks(c):
     return {
