@@ -10,9 +10,17 @@ others are replaced by `torch.nn.Identity` (the paper removes them; keeping the 
 every index and name of the container valid).  One call, no change to the model's code -- the
 paper's Listing 3.
 
-Only `Sequential` containers are rewritten: they are the only modules whose children are known to
-execute in order, one feeding the next.  Everything else (convolutions, the model's own `forward`)
-keeps running in PyTorch.
+`optimize` rewrites `Sequential` containers only: they are the only modules whose children are
+known to execute in order, one feeding the next.  Everything else (convolutions, the model's own
+`forward`) keeps running in PyTorch.
+
+`optimize_graph(model)` sees through hand-written `forward` methods as well: it records the model's
+data flow with `torch.fx`, follows every chain of optimizable operations -- layer modules, their
+functional forms (`F.relu`, `F.max_pool2d`, ...) and tensor additions written as `a + b`,
+`a += b` or `torch.add(a, b)` -- and replaces each chain by one `BrainSlugStack` call whose extra
+arguments are the residual operands.  This covers the residual blocks of a ResNet (BatchNorm ->
+Add -> ReLU) and the pre-activation / transition layers of a DenseNet, whose layers are not
+children of one `Sequential`.
 
 A `BrainSlugStack` plans lazily, once per input shape and dtype (the scheduler of Section 4.2: it
 computes the output size, asks the framework for the memory and launches the kernels on the
@@ -31,7 +39,8 @@ from torch import nn
 from . import brainslug as bs
 from . import workloads as wl
 
-__all__ = ["optimize", "BrainSlugStack", "layer_desc", "find_runs", "resolve_layers"]
+__all__ = ["optimize", "optimize_graph", "find_chains", "BrainSlugStack", "layer_desc", "find_runs",
+           "resolve_layers"]
 
 
 def _pair(v) -> Tuple[int, int]:
@@ -126,11 +135,25 @@ class BrainSlugStack(nn.Module):
     """A run of optimizable layers executed depth-first by the HIP library."""
 
     def __init__(self, modules: List[nn.Module], **plan_opts):
-        super().__init__()
-        self.replaced = [type(m).__name__ for m in modules]
-        self.layers = [d for d in (layer_desc(m) for m in modules) if d]
-        if any(d is None for d in (layer_desc(m) for m in modules)) or not self.layers:
+        descs = [layer_desc(m) for m in modules]
+        if any(d is None for d in descs):
             raise ValueError("BrainSlugStack needs a non-empty run of optimizable layers")
+        self._init([d for d in descs if d], [type(m).__name__ for m in modules], plan_opts)
+
+    @classmethod
+    def from_layers(cls, layers: List[dict], replaced: List[str], **plan_opts) -> "BrainSlugStack":
+        """A stack from layer descriptions (see `layer_desc`); `replaced` names what it stands for."""
+        self = cls.__new__(cls)
+        self._init([dict(l) for l in layers if l], list(replaced), plan_opts)
+        return self
+
+    def _init(self, layers, replaced, plan_opts):
+        nn.Module.__init__(self)
+        if not layers:
+            raise ValueError("BrainSlugStack needs a non-empty run of optimizable layers")
+        self.replaced = replaced
+        self.layers = layers
+        self.n_residuals = sum(1 for l in layers if l["kind"] == "add")
         self.channels = next((len(l["gamma"]) for l in self.layers if l["kind"] == "bn"), None)
         self.plan_opts = dict(plan_opts)
         self._plans: Dict[tuple, bs.Stack] = {}
@@ -146,11 +169,14 @@ class BrainSlugStack(nn.Module):
             name = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}.get(dtype)
             if name is None:
                 raise TypeError(f"BrainSlugStack supports float32, bfloat16 and float16 tensors, not {dtype}")
-            st = bs.Stack(resolve_layers(self.layers, key[0]), key[0], name).plan(**self.plan_opts)
+            layers = resolve_layers(self.layers, key[0])
+            st = bs.Stack(layers, key[0], name).plan(**self.plan_opts)
+            st.layers = layers
             self._plans[key] = st
         return st
 
-    def forward(self, x: torch.Tensor) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, *residuals: torch.Tensor) -> torch.Tensor:
+        """`residuals`: the second operand of every Add layer of the stack, in layer order."""
         if self.training:
             raise RuntimeError("BrainSlugStack implements the inference forward pass only: call model.eval()")
         if not x.is_cuda or x.dim() != 4:
@@ -162,7 +188,15 @@ class BrainSlugStack(nn.Module):
             # a channel slice of a concatenation buffer is read in place; other layouts are copied
             if bs.batch_stride(x) is None or (x.data_ptr() % 16) or (x.stride(0) * x.element_size()) % 16:
                 x = x.contiguous()
-            out, _ = st.run(x, indices=[])
+            if len(residuals) != self.n_residuals:
+                raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
+            res = []
+            for r, want in zip(residuals, wl.residual_shapes(st.layers, x.shape)):
+                if tuple(r.shape) != tuple(want) or r.dtype != x.dtype or r.device != x.device:
+                    raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
+                                       f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
+                res.append(r.contiguous())
+            out, _ = st.run(x, res, indices=[])
         return out
 
     def close(self) -> None:
@@ -190,3 +224,229 @@ def optimize(model: nn.Module, min_layers: int = 1, **plan_opts) -> nn.Module:
                 parent._modules[n] = nn.Identity()
             model.optimized_stacks.append(stack)
     return model
+
+
+# ---------------------------------------------------------------------------- data-flow graphs
+def _fn_args(node, names, defaults):
+    """Positional / keyword arguments of a call node as a dict over `names`."""
+    vals = dict(zip(names, node.args))
+    vals.update(node.kwargs)
+    if set(vals) - set(names):
+        return None
+    return {n: vals.get(n, defaults.get(n)) for n in names}
+
+
+def _const(v) -> bool:
+    """True when an argument is a plain Python value (not computed in the graph)."""
+    from torch import fx
+    if isinstance(v, fx.Node):
+        return False
+    if isinstance(v, (tuple, list)):
+        return all(_const(e) for e in v)
+    return v is None or isinstance(v, (int, float, bool))
+
+
+def _node_desc(node, modules):
+    """(layer dict or {} , main input node, residual node or None, display name) for an fx node
+    the library can take, else None."""
+    import operator
+
+    import torch.nn.functional as F
+    from torch import fx
+
+    def unary(desc, name, a):
+        return (desc, a, None, name) if isinstance(a, fx.Node) else None
+
+    if node.op == "call_module":
+        m = modules.get(node.target)
+        if m is None or isinstance(m, BrainSlugStack) or len(node.args) != 1 or node.kwargs:
+            return None
+        d = layer_desc(m)
+        return None if d is None else unary(d, type(m).__name__, node.args[0])
+
+    if node.op == "call_function":
+        t = node.target
+        if t in (operator.add, operator.iadd, torch.add):
+            if len(node.args) != 2 or (node.kwargs and node.kwargs.get("alpha", 1) != 1) or \
+                    set(node.kwargs) - {"alpha"}:
+                return None
+            a, b = node.args
+            if not (isinstance(a, fx.Node) and isinstance(b, fx.Node)) or a is b:
+                return None  # a tensor plus a number, or x + x: not a residual Add
+            return ({"kind": "add"}, a, b, "add")
+        if t in (F.relu, torch.relu, torch.relu_, F.relu_):
+            v = _fn_args(node, ["input", "inplace"], {"inplace": False})
+            return None if v is None or not _const(v["inplace"]) else unary({"kind": "relu"}, "relu", v["input"])
+        if t is F.leaky_relu:
+            v = _fn_args(node, ["input", "negative_slope", "inplace"], {"negative_slope": 0.01, "inplace": False})
+            if v is None or not _const(v["negative_slope"]):
+                return None
+            return unary({"kind": "leaky_relu", "slope": float(v["negative_slope"])}, "leaky_relu", v["input"])
+        if t is F.relu6:
+            v = _fn_args(node, ["input", "inplace"], {"inplace": False})
+            return None if v is None else unary({"kind": "clamp", "lo": 0.0, "hi": 6.0}, "relu6", v["input"])
+        if t is F.hardtanh:
+            v = _fn_args(node, ["input", "min_val", "max_val", "inplace"], {"min_val": -1.0, "max_val": 1.0, "inplace": False})
+            if v is None or not (_const(v["min_val"]) and _const(v["max_val"])):
+                return None
+            return unary({"kind": "clamp", "lo": float(v["min_val"]), "hi": float(v["max_val"])}, "hardtanh", v["input"])
+        if t is F.max_pool2d:
+            v = _fn_args(node, ["input", "kernel_size", "stride", "padding", "dilation", "ceil_mode", "return_indices"],
+                         {"stride": None, "padding": 0, "dilation": 1, "ceil_mode": False, "return_indices": False})
+            if v is None or not all(_const(v[k]) for k in v if k != "input") or v["return_indices"]:
+                return None
+            if _pair(v["dilation"]) != (1, 1):
+                return None
+            k = _pair(v["kernel_size"])
+            d = {"kind": "maxpool", "k": k, "s": _pair(v["stride"] if v["stride"] not in (None, [], ()) else k),
+                 "p": _pair(v["padding"]), "return_indices": False, "ceil_mode": bool(v["ceil_mode"])}
+            return unary(d, "max_pool2d", v["input"])
+        if t is F.avg_pool2d:
+            v = _fn_args(node, ["input", "kernel_size", "stride", "padding", "ceil_mode", "count_include_pad",
+                                "divisor_override"],
+                         {"stride": None, "padding": 0, "ceil_mode": False, "count_include_pad": True,
+                          "divisor_override": None})
+            if v is None or not all(_const(v[k]) for k in v if k != "input") or v["divisor_override"] is not None:
+                return None
+            k = _pair(v["kernel_size"])
+            d = {"kind": "avgpool", "k": k, "s": _pair(v["stride"] if v["stride"] not in (None, [], ()) else k),
+                 "p": _pair(v["padding"]), "count_include_pad": bool(v["count_include_pad"]),
+                 "ceil_mode": bool(v["ceil_mode"])}
+            return unary(d, "avg_pool2d", v["input"])
+        if t in (F.adaptive_avg_pool2d, F.adaptive_max_pool2d):
+            v = _fn_args(node, ["input", "output_size", "return_indices"], {"return_indices": False})
+            if v is None or not _const(v["output_size"]) or v["return_indices"]:
+                return None
+            o = v["output_size"]
+            o = tuple(o) if isinstance(o, (tuple, list)) else (o, o)
+            kind = "adaptive_avg" if t is F.adaptive_avg_pool2d else "adaptive_max"
+            return unary({"kind": kind, "out": o}, t.__name__, v["input"])
+        return None
+
+    if node.op == "call_method":
+        if node.target in ("add", "add_") and len(node.args) == 2 and not node.kwargs:
+            a, b = node.args
+            if isinstance(a, fx.Node) and isinstance(b, fx.Node) and a is not b:
+                return ({"kind": "add"}, a, b, node.target)
+            return None
+        if node.target in ("relu", "relu_") and len(node.args) == 1 and not node.kwargs:
+            return unary({"kind": "relu"}, node.target, node.args[0])
+    return None
+
+
+def _writes_in_place(node, modules) -> bool:
+    """Does the operation overwrite its first operand (ReLU(inplace=True), `a += b`, `relu_`)?"""
+    import operator
+
+    if node.op == "call_module":
+        return bool(getattr(modules.get(node.target), "inplace", False))
+    if node.op == "call_method":
+        return node.target.endswith("_")
+    if node.op == "call_function":
+        if node.target in (operator.iadd, operator.isub, operator.imul, operator.itruediv, torch.relu_,
+                           torch.nn.functional.relu_) or node.kwargs.get("out") is not None:
+            return True
+        F = torch.nn.functional
+        if node.target in (F.relu, F.leaky_relu, F.relu6, F.hardtanh):  # `inplace` is their last parameter
+            last = node.args[-1] if len(node.args) > 1 and isinstance(node.args[-1], bool) else False
+            return bool(node.kwargs.get("inplace", last))
+    return False
+
+
+class Chain:
+    """One chain of optimizable graph nodes: `nodes[i + 1]` consumes `nodes[i]` and nothing else does."""
+
+    def __init__(self, source):
+        self.source = source      # node that produces the chain's input
+        self.nodes = []           # graph nodes, in execution order
+        self.layers = []          # their layer descriptions ({} for inference-time identities)
+        self.names = []
+        self.residuals = []       # second operand of every Add, in order
+
+    def real_layers(self) -> int:
+        return sum(1 for l in self.layers if l)
+
+
+def find_chains(gm) -> List[Chain]:
+    """Aggregation detection on a traced model (Figure 4 on a data-flow graph instead of a layer
+    list): maximal chains of optimizable nodes in which every intermediate result has exactly one
+    consumer, the next node of the chain.  For an addition the chain continues through the operand
+    that ends a chain (the first one if both do); the other operand is a residual input."""
+    modules = dict(gm.named_modules())
+    tail_of: Dict[object, Chain] = {}   # node that currently ends an open chain -> chain
+    chains: List[Chain] = []
+    for node in gm.graph.nodes:
+        d = _node_desc(node, modules)
+        if d is None:
+            continue
+        desc, a, b, name = d
+        if _writes_in_place(node, modules) and len(a.users) > 1:
+            # the model overwrites a tensor that something else reads as well: what that reader
+            # sees depends on execution order, which a fused chain would change.  Left to PyTorch.
+            continue
+
+        def extendable(n):
+            return n is not None and n in tail_of and len(n.users) == 1
+
+        if b is not None and not extendable(a) and extendable(b):
+            a, b = b, a  # addition commutes bit for bit: continue the chain that ends in b
+        if extendable(a):
+            ch = tail_of.pop(a)
+        else:
+            ch = Chain(a)
+            chains.append(ch)
+        ch.nodes.append(node)
+        ch.layers.append(desc)
+        ch.names.append(name)
+        if b is not None:
+            ch.residuals.append(b)
+        tail_of[node] = ch
+    # A chain runs where its last node stood.  Should the model overwrite one of the chain's
+    # inputs between the chain's first and last node, the chain would read the new contents
+    # where the model read the old: such chains are left to PyTorch.
+    order = {n: i for i, n in enumerate(gm.graph.nodes)}
+
+    def overwritten(ch):
+        lo, hi = order[ch.nodes[0]], order[ch.nodes[-1]]
+        for v in [ch.source, *ch.residuals]:
+            for u in v.users:
+                if lo < order[u] < hi and u not in ch.nodes and u.args and u.args[0] is v and \
+                        _writes_in_place(u, modules):
+                    return True
+        return False
+
+    return [c for c in chains if c.real_layers() > 0 and not overwritten(c)]
+
+
+def optimize_graph(model: nn.Module, min_layers: int = 1, concrete_args=None, **plan_opts):
+    """Trace `model` with `torch.fx` and return a `GraphModule` in which every chain of at least
+    `min_layers` optimizable operations (see `find_chains`) is one BrainSlugStack call.  The model
+    itself is not modified; parameters and sub-modules that stay are shared with it.  Models whose
+    `forward` depends on tensor values cannot be traced (a `torch.fx` restriction): use `optimize`
+    on those.  `plan_opts` are passed to `bs_stack_plan`."""
+    from torch import fx
+
+    gm = model if isinstance(model, fx.GraphModule) else fx.symbolic_trace(model, concrete_args=concrete_args)
+    stacks = []
+    now: Dict[object, object] = {}  # last node of a replaced chain -> the call that stands for it
+    for i, ch in enumerate(find_chains(gm)):
+        if ch.real_layers() < min_layers:
+            continue
+        stack = BrainSlugStack.from_layers(ch.layers, ch.names, **plan_opts)
+        stack.train(model.training)
+        name = f"brainslug_stack_{i}"
+        gm.add_submodule(name, stack)
+        last = ch.nodes[-1]
+        # every residual operand is computed before its Add and so before the chain's last node
+        with gm.graph.inserting_after(last):
+            call = gm.graph.call_module(name, args=tuple(now.get(n, n) for n in (ch.source, *ch.residuals)))
+        last.replace_all_uses_with(call)
+        now[last] = call
+        for n in reversed(ch.nodes):
+            gm.graph.erase_node(n)
+        stacks.append(stack)
+    gm.graph.lint()
+    gm.recompile()
+    gm.delete_all_unused_submodules()
+    gm.optimized_stacks = stacks
+    return gm

@@ -11,6 +11,7 @@ import copy
 import numpy as np
 import pytest
 import torch
+import torch.nn.functional as F
 from torch import nn
 
 from oracle import breadth_first as bf
@@ -144,7 +145,230 @@ def test_adaptive_pools_ceil_mode_and_further_activations_are_taken():
         fe.resolve_layers([{"kind": "adaptive_avg", "out": (3, 3)}], (1, 1, 7, 7))
 
 
+# ------------------------------------------------------------------ data-flow graphs
+def _randomize_bn(model, seed):
+    g = torch.Generator().manual_seed(seed)
+    for mod in model.modules():
+        if isinstance(mod, nn.BatchNorm2d):
+            c = mod.num_features
+            mod.running_mean.copy_(torch.randn(c, generator=g) * 0.5)
+            mod.running_var.copy_(torch.rand(c, generator=g) * 1.5 + 0.5)
+            mod.weight.data.copy_(torch.rand(c, generator=g) + 0.5)
+            mod.bias.data.copy_(torch.randn(c, generator=g) * 0.1)
+    return model
+
+
+class ResBlock(nn.Module):
+    """A residual block with a hand-written forward: BatchNorm -> (+ identity) -> ReLU."""
+
+    def __init__(self, c, down=False):
+        super().__init__()
+        self.conv1 = nn.Conv2d(c, c, 3, padding=1, stride=2 if down else 1)
+        self.bn1 = nn.BatchNorm2d(c)
+        self.relu = nn.ReLU(inplace=True)
+        self.conv2 = nn.Conv2d(c, c, 3, padding=1)
+        self.bn2 = nn.BatchNorm2d(c)
+        self.down = nn.Sequential(nn.Conv2d(c, c, 1, stride=2), nn.BatchNorm2d(c)) if down else None
+
+    def forward(self, x):
+        identity = x
+        out = self.relu(self.bn1(self.conv1(x)))
+        out = self.bn2(self.conv2(out))
+        if self.down is not None:
+            identity = self.down(x)
+        out += identity
+        return self.relu(out)
+
+
+class ResNetLike(nn.Module):
+    def __init__(self, c=8):
+        super().__init__()
+        self.conv = nn.Conv2d(3, c, 3, padding=1)
+        self.bn = nn.BatchNorm2d(c)
+        self.pool = nn.MaxPool2d(3, 2, 1)
+        self.b1, self.b2 = ResBlock(c), ResBlock(c, down=True)
+        self.fc = nn.Linear(c, 4)
+
+    def forward(self, x):
+        x = self.pool(F.relu(self.bn(self.conv(x))))
+        x = self.b2(self.b1(x))
+        x = F.adaptive_avg_pool2d(x, 1)
+        return self.fc(torch.flatten(x, 1))
+
+
+class DenseLayer(nn.Module):
+    def __init__(self, c_in, growth):
+        super().__init__()
+        self.norm1 = nn.BatchNorm2d(c_in)
+        self.conv1 = nn.Conv2d(c_in, 2 * growth, 1)
+        self.norm2 = nn.BatchNorm2d(2 * growth)
+        self.conv2 = nn.Conv2d(2 * growth, growth, 3, padding=1)
+
+    def forward(self, feats):
+        x = self.conv1(F.relu(self.norm1(torch.cat(feats, 1))))
+        return self.conv2(F.relu(self.norm2(x), inplace=True))
+
+
+class DenseNetLike(nn.Module):
+    def __init__(self, c=8, growth=8):
+        super().__init__()
+        self.stem = nn.Conv2d(3, c, 3, padding=1)
+        self.norm0 = nn.BatchNorm2d(c)
+        self.layers = nn.ModuleList([DenseLayer(c + i * growth, growth) for i in range(2)])
+        c2 = c + 2 * growth
+        self.tnorm = nn.BatchNorm2d(c2)
+        self.tconv = nn.Conv2d(c2, c2 // 2, 1)
+        self.tpool = nn.AvgPool2d(2, 2)
+        self.norm5 = nn.BatchNorm2d(c2 // 2)
+        self.fc = nn.Linear(c2 // 2, 3)
+
+    def forward(self, x):
+        x = F.max_pool2d(torch.relu(self.norm0(self.stem(x))), 3, stride=2, padding=1)
+        feats = [x]
+        for layer in self.layers:
+            feats.append(layer(feats))
+        x = self.tpool(self.tconv(self.tnorm(torch.cat(feats, 1)).relu()))
+        x = F.adaptive_avg_pool2d(F.relu(self.norm5(x)), (1, 1))
+        return self.fc(torch.flatten(x, 1))
+
+
+def _models():
+    torch.manual_seed(3)
+    return {"resnet": _randomize_bn(ResNetLike(), 1).eval(), "densenet": _randomize_bn(DenseNetLike(), 2).eval()}
+
+
+def test_chains_are_found_through_hand_written_forwards():
+    m = _models()
+    g = fe.optimize_graph(m["resnet"])
+    assert [(s.replaced, s.n_residuals) for s in g.optimized_stacks] == [
+        (["BatchNorm2d", "relu", "MaxPool2d"], 0),
+        (["BatchNorm2d", "ReLU"], 0),
+        (["BatchNorm2d", "add", "ReLU"], 1),
+        (["BatchNorm2d", "ReLU"], 0),
+        (["BatchNorm2d", "add", "ReLU", "adaptive_avg_pool2d"], 1),
+        (["BatchNorm2d"], 0)]
+    kinds = [type(mod).__name__ for mod in g.modules()]
+    assert "BatchNorm2d" not in kinds and "ReLU" not in kinds and "MaxPool2d" not in kinds
+    assert kinds.count("Conv2d") == 6 and kinds.count("BrainSlugStack") == 6
+    # the original model is untouched, and short chains can be left to PyTorch
+    assert isinstance(m["resnet"].bn, nn.BatchNorm2d)
+    g2 = fe.optimize_graph(m["resnet"], min_layers=2)
+    assert len(g2.optimized_stacks) == 5 and "BatchNorm2d" in [type(mod).__name__ for mod in g2.modules()]
+    g = fe.optimize_graph(m["densenet"])
+    assert [s.replaced for s in g.optimized_stacks] == [
+        ["BatchNorm2d", "relu", "max_pool2d"], ["BatchNorm2d", "relu"], ["BatchNorm2d", "relu"],
+        ["BatchNorm2d", "relu"], ["BatchNorm2d", "relu"], ["BatchNorm2d", "relu"],
+        ["AvgPool2d", "BatchNorm2d", "relu", "adaptive_avg_pool2d"]]  # the transition's pool feeds the head
+
+
+@pytest.mark.parametrize("name", ["resnet", "densenet"])
+def test_chain_descriptions_reproduce_the_torch_model(name):
+    """Pin of the chain extraction (layer order, parameters, which operand of an addition is
+    the residual): every value of the traced torch model is recorded; the oracle, fed a chain's
+    recorded input and residual operands, must give the chain's recorded output."""
+    from torch import fx
+
+    model = _models()[name]
+    gm = fx.symbolic_trace(model)
+    values = {}
+
+    class Recorder(fx.Interpreter):
+        def run_node(self, n):
+            v = super().run_node(n)
+            values[n] = v.clone() if isinstance(v, torch.Tensor) else v  # before anything overwrites it
+            return v
+
+    with torch.no_grad():
+        Recorder(gm).run(torch.randn(2, 3, 20, 24, generator=torch.Generator().manual_seed(9)))
+    chains = fe.find_chains(gm)
+    assert len(chains) == (6 if name == "resnet" else 7)
+    for ch in chains:
+        xin = values[ch.source].numpy()
+        layers = fe.resolve_layers([l for l in ch.layers if l], xin.shape)
+        got, _, _ = bf.run_stack(layers, np.ascontiguousarray(xin), [values[r].numpy() for r in ch.residuals])
+        want = values[ch.nodes[-1]].numpy()
+        assert got.shape == want.shape
+        assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(want).max()), ch.names
+
+
+class Hazards(nn.Module):
+    def __init__(self):
+        super().__init__()
+        self.conv = nn.Conv2d(3, 4, 1)
+        self.relu_ = nn.ReLU(inplace=True)
+        self.bn = nn.BatchNorm2d(4)
+
+    def forward(self, x):
+        a = self.conv(x)
+        b = self.relu_(a)       # overwrites a, which the next line reads as well
+        c = self.bn(a) + b
+        d = c + c               # not a residual addition
+        e = d + 1.0             # a number, not a tensor
+        return F.relu(e), F.max_pool2d(e, 2, return_indices=True)
+
+
+class LateOverwrite(nn.Module):
+    def __init__(self):
+        super().__init__()
+        self.bn = nn.BatchNorm2d(4)
+
+    def forward(self, x):
+        a = x * 2.0
+        b = self.bn(a)      # reads a ...
+        a.mul_(3.0)         # ... which is overwritten before the chain that starts at bn ends
+        return torch.relu(b + a)
+
+
+def test_chain_whose_input_is_overwritten_midway_stays_in_pytorch():
+    m = LateOverwrite().eval()
+    g = fe.optimize_graph(m)
+    assert g.optimized_stacks == []
+    x = torch.randn(1, 4, 3, 3)
+    assert torch.equal(g(x), m(x))
+
+
+def test_what_the_graph_front_end_leaves_alone():
+    g = fe.optimize_graph(Hazards().eval())
+    assert [s.replaced for s in g.optimized_stacks] == [["BatchNorm2d", "add"], ["relu"]]
+    text = str(g.graph)
+    assert "relu_" in text and "max_pool2d" in text and text.count("operator.add") + text.count("_operator.add") >= 2
+    x = torch.randn(1, 3, 4, 4)
+    with pytest.raises(RuntimeError, match="GPU"):
+        g(x)
+    # a chain has its residual operands in layer order and refuses other shapes
+    st = fe.BrainSlugStack.from_layers([{"kind": "add"}, {"kind": "relu"}, {"kind": "add"}], ["add", "relu", "add"])
+    assert st.n_residuals == 2
+
+
 # ------------------------------------------------------------------ GPU
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["resnet", "densenet"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_graph_rewritten_model_matches_the_original_and_the_oracle(name, dtype):
+    ref = _models()[name].cuda().to(dtype)
+    opt = fe.optimize_graph(ref)
+    seen = {}
+    for i, stack in enumerate(opt.optimized_stacks):
+        stack.register_forward_hook(
+            lambda mod, inp, out, i=i: seen.__setitem__(i, ([t.detach().clone() for t in inp], out.detach().clone())))
+    x = torch.randn(3, 3, 36, 40, device="cuda").to(dtype)
+    with torch.no_grad():
+        want = ref(x).float()
+        got = opt(x).float()
+    tol = 1e-4 if dtype == torch.float32 else 2e-2
+    assert (got - want).abs().max().item() <= tol * max(1.0, want.abs().max().item())
+    assert len(seen) == len(opt.optimized_stacks)
+    dt = "f32" if dtype == torch.float32 else "f16"
+    for i, stack in enumerate(opt.optimized_stacks):
+        inp, out = seen[i]
+        layers = fe.resolve_layers(stack.layers, inp[0].shape)
+        expect, _, _ = bf.run_stack(layers, inp[0].float().cpu().numpy(),
+                                    [t.float().cpu().numpy() for t in inp[1:]], dt)
+        assert np.array_equal(out.float().cpu().numpy().view(np.uint32), expect.view(np.uint32)), stack.replaced
+    for s in opt.optimized_stacks:
+        s.close()
+
+
 @pytest.mark.gpu
 def test_head_like_model_on_the_gpu():
     ref = head_like(c=16).cuda()
