@@ -374,6 +374,7 @@ class Stack:
         self.n_res = bs_stack_num_residuals(self.handle)
         self.n_idx = bs_stack_num_index_outputs(self.handle)
         self._workspace = None
+        self._workspace_bytes = 0
 
     def close(self):
         if getattr(self, "handle", None):
@@ -385,6 +386,7 @@ class Stack:
     def plan(self, **opts):
         bs_stack_plan(self.handle, **opts)
         self._workspace = None
+        self._workspace_bytes = bs_stack_workspace_bytes(self.handle)
         return self
 
     def info(self) -> dict:
@@ -409,7 +411,7 @@ class Stack:
 
     def workspace(self, device="cuda"):
         import torch
-        n = bs_stack_workspace_bytes(self.handle)
+        n = self._workspace_bytes
         if n and (self._workspace is None or self._workspace.numel() < n):
             self._workspace = torch.empty(n, dtype=torch.uint8, device=device)
         return self._workspace if n else None

@@ -172,6 +172,7 @@ class BrainSlugStack(nn.Module):
             layers = resolve_layers(self.layers, key[0])
             st = bs.Stack(layers, key[0], name).plan(**self.plan_opts)
             st.layers = layers
+            st.res_shapes = [tuple(v) for v in wl.residual_shapes(layers, key[0])]
             self._plans[key] = st
         return st
 
@@ -191,7 +192,7 @@ class BrainSlugStack(nn.Module):
             if len(residuals) != self.n_residuals:
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
             res = []
-            for r, want in zip(residuals, wl.residual_shapes(st.layers, x.shape)):
+            for r, want in zip(residuals, st.res_shapes):
                 if tuple(r.shape) != tuple(want) or r.dtype != x.dtype or r.device != x.device:
                     raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
                                        f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
