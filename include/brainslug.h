@@ -19,7 +19,7 @@
  *     bs_stack_destroy
  *
  * Conventions
- *   - Tensors are dense NCHW, float32 or bfloat16 (bs_dtype).  All tensors of one
+ *   - Tensors are dense, NCHW or (a plan option) NHWC, float32, bfloat16 or float16 (bs_dtype).  All tensors of one
  *     stack share the dtype; BatchNorm parameters are always float32.
  *   - "host" / "device" at each pointer says where the memory lives.  The caller
  *     owns every buffer it passes; the library copies what it keeps.
@@ -130,8 +130,16 @@ typedef enum bs_variant {
     BS_VARIANT_POOL_DIRECT = 2, /* one step, disjoint windows (k == s, p == 0): registers only   */
     BS_VARIANT_LDS_TILE = 3,    /* tiles with halos staged in LDS, ping-pong buffers, barriers   */
     BS_VARIANT_POOL_ROWS = 4,   /* one or two pooling steps with overlapping / padded windows: rows slide in registers, no LDS */
-    BS_VARIANT_PLANE_POOL = 5   /* one step whose window is the whole (small) plane: one lane per plane       */
+    BS_VARIANT_PLANE_POOL = 5,  /* one step whose window is the whole (small) plane: one lane per plane       */
+    BS_VARIANT_NHWC_STREAM = 6, /* channels-last plans only: element-wise, one channel vector per lane   */
+    BS_VARIANT_NHWC_POOL = 7    /* channels-last plans only: one pooling step, a lane = one output pixel x one channel vector */
 } bs_variant;
+
+/* Memory order of every tensor of a planned stack (shapes are always given as N, C, H, W). */
+typedef enum bs_layout {
+    BS_LAYOUT_NCHW = 0, /* N, C, H, W: the width is contiguous                                       */
+    BS_LAYOUT_NHWC = 1  /* N, H, W, C: the channels of a pixel are contiguous ("channels last")      */
+} bs_layout;
 
 /*
  * Planner options; NULL or all-zero = automatic.
@@ -155,6 +163,13 @@ typedef enum bs_variant {
  *                           build fails the plan falls back to the slower kernels that read
  *                           shapes at run time.  1 = required: a failed build makes
  *                           bs_stack_plan return BS_ERR_JIT.  -1 = off for this plan.
+ *   layout                  bs_layout of the input, the residual operands, the output and the
+ *                           index outputs.  BS_LAYOUT_NHWC plans run one step (one pooling
+ *                           operation with the element-wise operations around it) per
+ *                           sequence and use their own two kernel families; force_variant
+ *                           must be automatic, tile options and jit are ignored, and
+ *                           bs_stack_run_strided accepts dense tensors only.  Index outputs
+ *                           hold the same values (ih * W + iw) in channels-last order.
  */
 typedef struct bs_plan_options {
     uint64_t max_lds_bytes;
@@ -166,7 +181,8 @@ typedef struct bs_plan_options {
     int32_t tile_rows, tile_cols, planes_per_group;
     int32_t host_only;
     int32_t jit;
-    int32_t reserved[4];
+    int32_t layout;
+    int32_t reserved[3];
 } bs_plan_options;
 
 typedef struct bs_plan_info {

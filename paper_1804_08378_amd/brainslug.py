@@ -21,7 +21,9 @@ BS_F32, BS_BF16, BS_F16 = 0, 1, 2
 BS_BATCHNORM, BS_RELU, BS_ADD, BS_MAXPOOL, BS_AVGPOOL, BS_LEAKY_RELU, BS_CLAMP = 1, 2, 3, 4, 5, 6, 7
 BS_VARIANT_AUTO, BS_VARIANT_STREAM, BS_VARIANT_POOL_DIRECT, BS_VARIANT_LDS_TILE = 0, 1, 2, 3
 BS_VARIANT_POOL_ROWS, BS_VARIANT_PLANE_POOL = 4, 5
-VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows", 5: "plane_pool"}
+VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows", 5: "plane_pool", 6: "nhwc_stream",
+                 7: "nhwc_pool"}
+BS_LAYOUT_NCHW, BS_LAYOUT_NHWC = 0, 1
 STATUS_NAMES = {
     0: "BS_OK", 1: "BS_ERR_NULL", 2: "BS_ERR_SHAPE", 3: "BS_ERR_PARAM", 4: "BS_ERR_UNSUPPORTED",
     5: "BS_ERR_NOT_PLANNED", 6: "BS_ERR_NO_FIT", 7: "BS_ERR_ALIGN", 8: "BS_ERR_WORKSPACE",
@@ -48,7 +50,8 @@ class bs_plan_options(C.Structure):
                 ("max_steps_per_sequence", C.c_int32), ("threads_per_group", C.c_int32),
                 ("num_cus", C.c_int32), ("breadth_first", C.c_int32), ("force_variant", C.c_int32),
                 ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("planes_per_group", C.c_int32),
-                ("host_only", C.c_int32), ("jit", C.c_int32), ("reserved", C.c_int32 * 4)]
+                ("host_only", C.c_int32), ("jit", C.c_int32), ("layout", C.c_int32),
+                ("reserved", C.c_int32 * 3)]
 
 
 class bs_plan_info(C.Structure):
@@ -375,6 +378,7 @@ class Stack:
         self.n_idx = bs_stack_num_index_outputs(self.handle)
         self._workspace = None
         self._workspace_bytes = 0
+        self.layout = BS_LAYOUT_NCHW
 
     def close(self):
         if getattr(self, "handle", None):
@@ -385,6 +389,7 @@ class Stack:
 
     def plan(self, **opts):
         bs_stack_plan(self.handle, **opts)
+        self.layout = int(opts.get("layout", BS_LAYOUT_NCHW))
         self._workspace = None
         self._workspace_bytes = bs_stack_workspace_bytes(self.handle)
         return self
@@ -404,8 +409,9 @@ class Stack:
 
     def alloc_outputs(self, device="cuda", indices=True):
         import torch
-        out = torch.empty(self.out_shape, dtype=self.torch_dtype(), device=device)
-        idx = [torch.empty(bs_stack_index_shape(self.handle, i), dtype=torch.int32, device=device)
+        mf = torch.channels_last if self.layout == BS_LAYOUT_NHWC else torch.contiguous_format
+        out = torch.empty(self.out_shape, dtype=self.torch_dtype(), device=device, memory_format=mf)
+        idx = [torch.empty(bs_stack_index_shape(self.handle, i), dtype=torch.int32, device=device, memory_format=mf)
                for i in range(self.n_idx)] if indices else []
         return out, idx
 
@@ -421,6 +427,8 @@ class Stack:
         `x` and `out` may be channel slices (t[:, a:b]) of larger contiguous tensors: they are
         read and written in place."""
         import torch
+        if self.layout == BS_LAYOUT_NHWC:
+            return self._run_nhwc(x, residuals, out, indices, stream)
         if tuple(x.shape) != self.in_shape or x.dtype != self.torch_dtype() or batch_stride(x) is None:
             raise ValueError("input must be a tensor of the stack's shape and dtype, contiguous or a "
                              "channel slice of a contiguous tensor")
@@ -444,4 +452,30 @@ class Stack:
         else:
             bs_stack_run_strided(self.handle, x.data_ptr(), batch_stride(x), res, out.data_ptr(),
                                  batch_stride(out), idx, wsp, wsn, st)
+        return out, indices
+
+    def _run_nhwc(self, x, residuals, out, indices, stream):
+        """A channels-last plan: every tensor is in torch's channels_last memory format."""
+        import torch
+        cl = torch.channels_last
+        if tuple(x.shape) != self.in_shape or x.dtype != self.torch_dtype() or not x.is_contiguous(memory_format=cl):
+            raise ValueError("input must be a channels_last tensor of the stack's shape and dtype")
+        for r in residuals:
+            if r.dtype != self.torch_dtype() or not r.is_contiguous(memory_format=cl):
+                raise ValueError("residuals must be channels_last tensors of the stack's dtype")
+        if out is None or indices is None:
+            o2, i2 = self.alloc_outputs(x.device, indices is None)
+            out = o2 if out is None else out
+            indices = i2 if indices is None else indices
+        if tuple(out.shape) != self.out_shape or out.dtype != self.torch_dtype() or \
+                not out.is_contiguous(memory_format=cl):
+            raise ValueError("out must be a channels_last tensor of the stack's output shape and dtype")
+        for t in indices or []:
+            if t is not None and not t.is_contiguous(memory_format=cl):
+                raise ValueError("index outputs must be channels_last tensors")
+        ws = self.workspace(x.device)
+        st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        idx = [t.data_ptr() if t is not None else 0 for t in indices] if indices else None
+        wsp, wsn = (ws.data_ptr(), ws.numel()) if ws is not None else (0, 0)
+        bs_stack_run(self.handle, x.data_ptr(), [r.data_ptr() for r in residuals], out.data_ptr(), idx, wsp, wsn, st)
         return out, indices

@@ -52,6 +52,7 @@ struct Sequence {
     PoolRowsK rows{};
     PoolRows2K rows2{};
     LdsSeqK lds{};
+    NhwcK nhwc{};
     // run-time build (hipFunction_t) without / with index outputs; null = pre-compiled kernel
     int32_t jit = 0;
     void *jit_fn[2] = {nullptr, nullptr};
@@ -121,6 +122,8 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
                           uint32_t in_extra, uint32_t out_extra, const void *const *res,
                           int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
+// bs_nhwc.hip: channels-last kernels (element-wise, and one pooling step per sequence)
+bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream);
 // bs_rows.hip: *_supported = the signature is in the pre-compiled table; *_buildable = the
 // kernel template can be instantiated for it at run time; *_expr = that instance's name
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);

@@ -177,6 +177,23 @@ struct PoolRows2K {
     FastDiv div_cbs, div_chunks, div_c;
 };
 
+// Channels-last (N, H, W, C in memory) sequences: element-wise only (pool.kind == 0, the list
+// in `pre`) or one pooling operation with element-wise operations before and after it.
+struct NhwcK {
+    const void *in;
+    void *out;
+    const float *params;
+    const void *res[K_MAX_RES];
+    int32_t *idx;
+    int32_t n_pre, n_post;
+    EwOp pre[K_MAX_STREAM_EW], post[K_MAX_EW];
+    PoolK pool;
+    int32_t C, H, W, Ho, Wo;
+    uint32_t total;   // lanes with work: (output) pixels * channel vectors
+    FastDiv div_cv;   // by channel vectors per pixel = C / vec
+    FastDiv div_wo, div_ho;
+};
+
 #if defined(__HIPCC__)
 #define BS_HD __host__ __device__ inline
 #else

@@ -494,6 +494,17 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         if (ls != BS_OK) return ls;
         break;
     }
+    case BS_VARIANT_NHWC_STREAM:
+    case BS_VARIANT_NHWC_POOL: {
+        if (in_extra != 0 || out_extra != 0) return BS_ERR_UNSUPPORTED;
+        NhwcK k = q.nhwc;
+        k.in = in; k.out = out; k.params = s->dev_params;
+        for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
+        k.idx = ip[0];
+        const bs_status ls = launch_nhwc(k, dtype, q.vec, q.grid, q.threads, stream);
+        if (ls != BS_OK) return ls;
+        break;
+    }
     default:
         return BS_ERR_UNSUPPORTED;
     }

@@ -32,6 +32,9 @@ bs_status build_operations(bs_stack *s)
         switch (L.desc.kind) {
         case BS_BATCHNORM:
             op.kind = OP_BN;
+            // tables start at a multiple of 8 floats: the channels-last kernels read them with
+            // 128-bit loads
+            while (s->host_params.size() % 8 != 0) s->host_params.push_back(0.0f);
             op.param_off = (int32_t)s->host_params.size();
             s->host_params.insert(s->host_params.end(), L.scale.begin(), L.scale.end());
             s->host_params.insert(s->host_params.end(), L.shift.begin(), L.shift.end());
@@ -403,6 +406,55 @@ static void plan_stream(const bs_stack *s, Sequence &q)
     q.redundancy = 1.0;
     q.tile_rows = q.tile_cols = 0;
     q.planes_per_group = 0;
+}
+
+// Channels-last sequence: element-wise only, or one pooling step.
+static bs_status plan_nhwc(const bs_stack *s, Sequence &q)
+{
+    NhwcK &k = q.nhwc;
+    k = NhwcK{};
+    const int32_t C = (int32_t)q.in_shape[1];
+    const int32_t vec = (C % vec_of(s) == 0) ? vec_of(s) : 1;
+    q.vec = vec;
+    bool seen = false;
+    for (int32_t i = q.first_op; i < q.first_op + q.n_ops; ++i) {
+        const Op &op = s->ops[i];
+        if (!op_is_elementwise(op.kind)) {
+            if (seen) return BS_ERR_UNSUPPORTED;  // one pooling operation per channels-last sequence
+            k.pool = make_pool(op, nullptr, q);
+            k.H = op.in_h; k.W = op.in_w; k.Ho = op.out_h; k.Wo = op.out_w;
+            seen = true;
+        } else if (op.kind != OP_AVGNORM) {
+            if (seen) {
+                if (k.n_post >= K_MAX_EW) return BS_ERR_UNSUPPORTED;
+                fill_ew(s, op, q, k.post[k.n_post++]);
+            } else {
+                if (k.n_pre >= (count_pools(s, q.first_op, q.n_ops) ? K_MAX_EW : K_MAX_STREAM_EW))
+                    return BS_ERR_UNSUPPORTED;
+                fill_ew(s, op, q, k.pre[k.n_pre++]);
+            }
+        }
+    }
+    k.C = C;
+    if (!seen) {
+        k.H = k.Ho = (int32_t)q.in_shape[2];
+        k.W = k.Wo = (int32_t)q.in_shape[3];
+    }
+    q.variant = seen ? BS_VARIANT_NHWC_POOL : BS_VARIANT_NHWC_STREAM;
+    const int64_t pixels = q.in_shape[0] * (int64_t)k.Ho * k.Wo;
+    k.total = (uint32_t)(pixels * (C / vec));
+    k.div_cv = make_fastdiv((uint32_t)(C / vec));
+    k.div_wo = make_fastdiv((uint32_t)k.Wo);
+    k.div_ho = make_fastdiv((uint32_t)k.Ho);
+    q.threads = std::min(q.threads, 256);
+    const int64_t per_group = (int64_t)q.threads * (seen ? 1 : K_STREAM_U);
+    q.grid = ((int64_t)k.total + per_group - 1) / per_group;
+    q.lds_bytes = 0;
+    q.redundancy = seen ? (double)k.Ho * k.pool.kh * k.Wo * k.pool.kw / ((double)k.H * k.W) : 1.0;
+    q.tile_rows = q.tile_cols = 0;
+    q.planes_per_group = 0;
+    q.n_levels = seen ? 1 : 0;
+    return BS_OK;
 }
 
 // One pooling operation whose window is the whole plane (global pooling), the plane small
@@ -986,7 +1038,12 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
         return BS_OK;
     };
     std::vector<SeqDraft> drafts;
-    if (o.max_steps_per_sequence > 0 || per_layer || o.force_variant != BS_VARIANT_AUTO) {
+    const bool nhwc = o.layout == BS_LAYOUT_NHWC;
+    if (nhwc) {
+        // channels-last kernels take one step (one pooling operation) per sequence
+        const bs_status fs = fill(1, drafts);
+        if (fs != BS_OK) return fs;
+    } else if (o.max_steps_per_sequence > 0 || per_layer || o.force_variant != BS_VARIANT_AUTO) {
         const bs_status fs = fill(o.max_steps_per_sequence, drafts);
         if (fs != BS_OK) return fs;
     } else {
@@ -1025,7 +1082,9 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
         const int32_t pools = count_pools(s, q.first_op, q.n_ops);
         q.n_levels = pools;
         bs_status st = BS_OK;
-        if (pools == 0) {
+        if (nhwc) {
+            st = plan_nhwc(s, q);
+        } else if (pools == 0) {
             plan_stream(s, q);
         } else if (direct_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {
             plan_direct(s, q);
@@ -1037,7 +1096,7 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             st = plan_lds(s, q, o, lim);
         }
         if (st != BS_OK) return st;
-        st = prepare_jit(s, q, o.host_only != 0);
+        if (!nhwc) st = prepare_jit(s, q, o.host_only != 0);
         if (st != BS_OK) return st;
         if (di + 1 < drafts.size()) {
             uint64_t bytes = (uint64_t)q.out_shape[0] * q.out_shape[1] * q.out_shape[2] * q.out_shape[3] * es;
@@ -1071,6 +1130,9 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (o.force_variant < 0 || o.force_variant > BS_VARIANT_PLANE_POOL) return BS_ERR_PARAM;
     if (o.max_lds_bytes > 64 * 1024) return BS_ERR_PARAM;
     if (o.jit < -1 || o.jit > 1) return BS_ERR_PARAM;
+    if (o.layout != BS_LAYOUT_NCHW && o.layout != BS_LAYOUT_NHWC) return BS_ERR_PARAM;
+    // channels-last plans have their own two kernels: nothing to force, no tiles to set
+    if (o.layout == BS_LAYOUT_NHWC && o.force_variant != BS_VARIANT_AUTO) return BS_ERR_PARAM;
 
     stack->planned = stack->device_planned = false;
     free_params(stack);

@@ -59,6 +59,9 @@ bs_status check_buffers(const bs_stack *stack, const void *in, int64_t &in_strid
     if (in_stride == 0) in_stride = (int64_t)in_image;
     if (out_stride == 0) out_stride = (int64_t)out_image;
     if (in_stride < (int64_t)in_image || out_stride < (int64_t)out_image) return BS_ERR_SHAPE;
+    // a channel slice of a channels-last tensor is not a batch-strided tensor
+    if (stack->opts.layout == BS_LAYOUT_NHWC && (in_stride != (int64_t)in_image || out_stride != (int64_t)out_image))
+        return BS_ERR_UNSUPPORTED;
     if (in_stride > 0x7fffffffll || out_stride > 0x7fffffffll) return BS_ERR_SHAPE;
     const Span sin{in, images, in_image * es, (uint64_t)in_stride * es};
     const Span sout{out, images, out_image * es, (uint64_t)out_stride * es};

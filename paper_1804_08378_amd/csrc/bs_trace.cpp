@@ -51,6 +51,8 @@ const char *variant_name(int32_t v)
     case BS_VARIANT_LDS_TILE: return "lds_tile";
     case BS_VARIANT_POOL_ROWS: return "pool_rows";
     case BS_VARIANT_PLANE_POOL: return "plane_pool";
+    case BS_VARIANT_NHWC_STREAM: return "nhwc_stream";
+    case BS_VARIANT_NHWC_POOL: return "nhwc_pool";
     }
     return "?";
 }

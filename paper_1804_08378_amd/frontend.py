@@ -161,16 +161,22 @@ class BrainSlugStack(nn.Module):
     def extra_repr(self) -> str:
         return "replaces " + " -> ".join(self.replaced)
 
-    def plan_for(self, shape, dtype: torch.dtype) -> bs.Stack:
-        """The planned stack for this input shape and dtype (cached)."""
-        key = (tuple(int(v) for v in shape), dtype)
+    def plan_for(self, shape, dtype: torch.dtype, channels_last: bool = False) -> bs.Stack:
+        """The planned stack for this input shape, dtype and memory format (cached)."""
+        key = (tuple(int(v) for v in shape), dtype, bool(channels_last))
         st = self._plans.get(key)
         if st is None:
             name = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}.get(dtype)
             if name is None:
                 raise TypeError(f"BrainSlugStack supports float32, bfloat16 and float16 tensors, not {dtype}")
             layers = resolve_layers(self.layers, key[0])
-            st = bs.Stack(layers, key[0], name).plan(**self.plan_opts)
+            opts = dict(self.plan_opts)
+            if channels_last:
+                # channels-last plans have their own kernels: options that pick or tune the
+                # NCHW ones do not apply
+                opts = {k: v for k, v in opts.items() if k in ("threads_per_group", "num_cus")}
+                opts["layout"] = bs.BS_LAYOUT_NHWC
+            st = bs.Stack(layers, key[0], name).plan(**opts)
             st.layers = layers
             st.res_shapes = [tuple(v) for v in wl.residual_shapes(layers, key[0])]
             self._plans[key] = st
@@ -185,9 +191,14 @@ class BrainSlugStack(nn.Module):
         if self.channels is not None and x.shape[1] != self.channels:
             raise RuntimeError(f"expected {self.channels} channels, got {x.shape[1]}")
         with torch.no_grad():
-            st = self.plan_for(x.shape, x.dtype)
+            # a channels_last tensor stays channels_last: the stack is planned for that memory
+            # order and its output is channels_last as well (what the convolutions around it use)
+            nhwc = not x.is_contiguous() and x.is_contiguous(memory_format=torch.channels_last)
+            st = self.plan_for(x.shape, x.dtype, nhwc)
+            mf = torch.channels_last if nhwc else torch.contiguous_format
             # a channel slice of a concatenation buffer is read in place; other layouts are copied
-            if bs.batch_stride(x) is None or (x.data_ptr() % 16) or (x.stride(0) * x.element_size()) % 16:
+            if not nhwc and (bs.batch_stride(x) is None or (x.data_ptr() % 16) or
+                             (x.stride(0) * x.element_size()) % 16):
                 x = x.contiguous()
             if len(residuals) != self.n_residuals:
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
@@ -196,7 +207,7 @@ class BrainSlugStack(nn.Module):
                 if tuple(r.shape) != tuple(want) or r.dtype != x.dtype or r.device != x.device:
                     raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
                                        f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
-                res.append(r.contiguous())
+                res.append(r.contiguous(memory_format=mf))
             out, _ = st.run(x, res, indices=[])
         return out
 

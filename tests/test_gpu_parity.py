@@ -621,6 +621,90 @@ def test_channel_slice_in_place_and_argument_errors():
     st.close()
 
 
+# ------------------------------------------------------------------ channels last
+def _check_nhwc(layers, x, res, dtype, label, **opts):
+    """The same stack on channels-last tensors: the oracle's numbers, in another memory order."""
+    print(f"[parity] nhwc/{label} shape={x.shape} dtype={dtype} opts={opts}", flush=True)
+    ref, ref_idx, _ = bf.run_stack(layers, x, res, dtype)
+    cl = torch.channels_last
+    st = bs.Stack(layers, x.shape, dtype).plan(layout=bs.BS_LAYOUT_NHWC, **opts)
+    out, idx = st.run(_dev(x, dtype).contiguous(memory_format=cl),
+                      [_dev(r, dtype).contiguous(memory_format=cl) for r in res])
+    torch.cuda.synchronize()
+    info = st.info()
+    st.close()
+    assert out.is_contiguous(memory_format=cl) and all(t.is_contiguous(memory_format=cl) for t in idx)
+    o = out.float().cpu().numpy()  # logical N, C, H, W values
+    ndiff = int((np.ascontiguousarray(o).view(np.uint32) != ref.view(np.uint32)).sum())
+    print(f"         non-identical={ndiff} variants={[q['variant_name'] for q in info['sequences']]}", flush=True)
+    assert o.shape == ref.shape and ndiff == 0, label
+    assert len(idx) == len(ref_idx)
+    for a, b in zip(idx, ref_idx):
+        assert np.array_equal(a.cpu().numpy(), b), label
+    assert info["n_sequences"] == info["n_steps"]
+    assert all(q["variant_name"] in ("nhwc_stream", "nhwc_pool") for q in info["sequences"])
+    return info
+
+
+NHWC_SHAPES = [(2, 8, 13, 11), (1, 16, 9, 16), (2, 12, 12, 10), (3, 5, 7, 9), (1, 24, 1, 1), (2, 8, 57, 31),
+               (1, 1, 6, 5)]
+
+
+@pytest.mark.parametrize("shape", NHWC_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_channels_last_plans_match_the_oracle(shape, dtype):
+    """Every stack family on channels-last tensors: channel counts that give 128-bit vectors
+    for both element sizes (8, 16, 24), for float32 only (12) and for neither (5, 1)."""
+    c = shape[1]
+    stacks = {}
+    for fam, d in (("s", _stacks(c)), ("r", _rows_stacks(c)), ("r2", _rows2_stacks(c)), ("c", _ceil_stacks(c))):
+        stacks.update({f"{fam}/{k}": v for k, v in d.items()})
+    stacks.update({"b/" + k: v[0] for k, v in _built_stacks(c).items()})
+    stacks.update({"a/" + k: v[0] for k, v in _activation_stacks(c).items()})
+    h, w = shape[2], shape[3]
+    stacks["g/avg_head"] = [wl.bn_params(c, 98), wl.relu(), wl.avgpool((h, w), (h, w), 0)]
+    stacks["g/max_head"] = [wl.leaky_relu(0.1), wl.maxpool((h, w), (1, 1), 0, True), wl.bn_params(c, 99)]
+    ran = 0
+    for name, layers in stacks.items():
+        cur, ok = shape, True
+        for l in layers:
+            if l["kind"] in ("maxpool", "avgpool") and (cur[2] + 2 * l["p"][0] < l["k"][0] or cur[3] + 2 * l["p"][1] < l["k"][1]):
+                ok = False
+                break
+            cur = wl.output_shape([l], cur)
+            ok = ok and cur[2] >= 1 and cur[3] >= 1
+        if not ok:
+            continue
+        x = wl.activation(shape, 110, dtype)
+        res = [wl.activation(sh, 111 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
+        _check_nhwc(layers, x, res, dtype, f"{name}{shape}")
+        ran += 1
+    assert ran >= 6
+
+
+@pytest.mark.parametrize("name,dtype", [("vgg_a", "f32"), ("resnet_stem", "bf16"), ("resnet_tail", "f16"),
+                                        ("densenet_trans", "f32"), ("halo_stress", "f32")])
+def test_channels_last_configs_reduced_batch(name, dtype):
+    layers, x, res = _shrunk(name, dtype, batch=2)
+    _check_nhwc(layers, x, res, dtype, name)
+
+
+def test_channels_last_argument_checks():
+    layers = [wl.bn_params(8, 3), wl.relu(), wl.maxpool(2, 2, 0, True)]
+    x = wl.activation((2, 8, 6, 8), 120)
+    st = bs.Stack(layers, x.shape, "f32").plan(layout=bs.BS_LAYOUT_NHWC)
+    xd = _dev(x, "f32")
+    with pytest.raises(ValueError, match="channels_last"):
+        st.run(xd)  # an NCHW tensor given to a channels-last plan
+    with pytest.raises(bs.BrainSlugError) as e:  # no batch strides for channels-last plans
+        bs.bs_stack_run_strided(st.handle, xd.data_ptr(), 8 * 6 * 8 + 64, None, xd.data_ptr() + (1 << 20), 0, None, 0, 0, 0)
+    assert e.value.status == 4
+    st.close()
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.Stack(layers, x.shape, "f32").plan(layout=bs.BS_LAYOUT_NHWC, force_variant=bs.BS_VARIANT_LDS_TILE)
+    assert e.value.status == 3
+
+
 # ------------------------------------------------------------------ further activations
 def _activation_stacks(c):
     return {

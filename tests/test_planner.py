@@ -239,3 +239,33 @@ def test_capacity_splits_keep_every_operation():
     assert info["n_operations"] == 50
     assert sum(s["n_operations"] for s in info["steps"]) == 50
     assert sum(q["n_layers"] for q in info["sequences"]) == 50
+
+
+def test_channels_last_plans_take_one_step_per_sequence():
+    """Host-only channels-last plans: a sequence per step, the two channels-last kernel families,
+    workspace between the sequences; options that belong to the NCHW kernels are refused."""
+    for name in ("vgg_a", "resnet_stem", "resnet_tail", "densenet_trans", "halo_stress"):
+        layers, shape, dtypes = wl.build(name)
+        for dtype in dtypes:
+            st = bs.Stack(layers, shape, dtype).plan(host_only=1, layout=bs.BS_LAYOUT_NHWC)
+            info = st.info()
+            assert info["n_sequences"] == info["n_steps"]
+            pools = sum(1 for l in layers if l["kind"] in ("maxpool", "avgpool"))
+            names = [q["variant_name"] for q in info["sequences"]]
+            assert names == (["nhwc_pool"] * pools if pools else ["nhwc_stream"])
+            assert (info["workspace_bytes"] > 0) == (pools > 1)
+            for q in info["sequences"]:
+                assert q["run_time_build"] == 0 and q["lds_bytes"] == 0 and q["grid"] >= 1
+            st.close()
+    h = bs.bs_stack_create([wl.relu()], (1, 4, 8, 8), "f32")
+    try:
+        for bad in (dict(layout=2), dict(layout=-1), dict(layout=1, force_variant=bs.BS_VARIANT_STREAM)):
+            with pytest.raises(bs.BrainSlugError) as e:
+                bs.bs_stack_plan(h, host_only=1, **bad)
+            assert e.value.status == 3
+        bs.bs_stack_plan(h, host_only=1, layout=1)
+        # a channels-last plan takes dense tensors only
+        assert bs.bs_stack_check_buffers(h, 4096, 4 * 8 * 8 + 64, None, 1 << 20, 0, None, 0, 0) == 4
+        assert bs.bs_stack_check_buffers(h, 4096, 0, None, 1 << 20, 0, None, 0, 0) == 0
+    finally:
+        bs.bs_stack_destroy(h)
