@@ -51,10 +51,12 @@ class StackBench:
         self.images = x.shape[0]
         tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
         self.fused = bs.Stack(layers, x.shape, dtype).plan(**plan_opts)
-        self.lbl = bs.Stack(layers, x.shape, dtype).plan(breadth_first=1)
+        nhwc = plan_opts.get("layout", 0) == bs.BS_LAYOUT_NHWC
+        self.lbl = bs.Stack(layers, x.shape, dtype).plan(breadth_first=1, layout=int(nhwc))
         self.sets = min(64, max(2, -(-min_rotation_bytes // self.bytes)))
-        x0 = torch.from_numpy(x).to(tdt).cuda()
-        r0 = [torch.from_numpy(r).to(tdt).cuda() for r in res]
+        mf = torch.channels_last if nhwc else torch.contiguous_format
+        x0 = torch.from_numpy(x).to(tdt).cuda().contiguous(memory_format=mf)
+        r0 = [torch.from_numpy(r).to(tdt).cuda().contiguous(memory_format=mf) for r in res]
         self.x = [x0] + [x0.clone() for _ in range(self.sets - 1)]
         self.res = [r0] + [[r.clone() for r in r0] for _ in range(self.sets - 1)]
         self.out, self.idx = [], []
@@ -352,6 +354,8 @@ def main():
     ap.add_argument("--streams", action="store_true",
                     help="enqueue the three independent stacks of a step on one HIP stream each (default priority) "
                          "instead of all on one stream: kernels then overlap at their edges")
+    ap.add_argument("--nhwc", action="store_true",
+                    help="also time every configuration with channels-last (NHWC) tensors and plans")
     ap.add_argument("--frontend", action="store_true",
                     help="also time the VGG stacks as torch modules, and a whole residual network with hand-written "
                          "forward methods: PyTorch eager against frontend.optimize() / optimize_graph()")
@@ -486,6 +490,30 @@ def main():
                     del sb
                     torch.cuda.empty_cache()
         out["all_configs"] = rows
+
+    if args.nhwc:
+        stacks = None
+        torch.cuda.empty_cache()
+        log("channels-last (NHWC) plans: one step per sequence")
+        log(f"{'config':<16}{'dtype':<6}{'sequences':<24}{'MB':>8}{'us mean':>9}{'us min':>8}{'GB/s':>8}{'%peak':>7}"
+            f"{'lbl us':>9}{'speedup':>8}")
+        rows = []
+        for name in wl.CONFIG_NAMES:
+            for dt in wl.build(name)[2]:
+                sb = StackBench(name, dt, layout=1)
+                m, p, mn = time_steps([sb], "fused", args.steps, args.warmup)
+                ml, pl, _ = time_steps([sb], "lbl", max(10, args.steps // 4), 2)
+                g = sb.bytes / (p[name] * 1e-3) / 1e9
+                seqs = "+".join(q["variant_name"] for q in sb.info["sequences"])
+                row = {"config": name, "dtype": dt, "sequences": seqs, "MB": sb.bytes / 1e6,
+                       "us_mean": p[name] * 1e3, "us_min": mn[name] * 1e3, "GBps": g,
+                       "pct_peak": 100 * g / HBM_PEAK_GBPS, "lbl_us": pl[name] * 1e3, "speedup": pl[name] / p[name]}
+                rows.append(row)
+                log(f"{name:<16}{dt:<6}{seqs:<24}{row['MB']:>8.1f}{row['us_mean']:>9.1f}{row['us_min']:>8.1f}{g:>8.0f}"
+                    f"{row['pct_peak']:>7.1f}{row['lbl_us']:>9.1f}{row['speedup']:>8.2f}")
+                del sb
+                torch.cuda.empty_cache()
+        out["nhwc_configs"] = rows
     print(json.dumps(out), flush=True)
 
 

@@ -123,6 +123,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
                           int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
 // bs_nhwc.hip: channels-last kernels (element-wise, and one pooling step per sequence)
+void nhwc_block(const PoolK &p, int32_t vec, int32_t dtype, int32_t &ohb, int32_t &owb);  // output pixels per lane
 bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream);
 // bs_rows.hip: *_supported = the signature is in the pre-compiled table; *_buildable = the
 // kernel template can be instantiated for it at run time; *_expr = that instance's name

@@ -6,9 +6,11 @@
 // parameters are per-lane vectors here (one 128-bit load of scale and of shift per lane).
 //
 //   nhwc_stream_kernel  element-wise only sequence, U vectors per lane.
-//   nhwc_pool_kernel    [element-wise]* pool [element-wise]*: a lane produces VEC channels of
-//                       one output pixel.  Overlapping windows re-read their shared cells
-//                       through the caches and recompute the element-wise operations on them.
+//   nhwc_pool_kernel    [element-wise]* pool [element-wise]* for the common windows (2x2/2,
+//                       3x3/2, 3x3/1): a lane produces VEC channels of a small block of
+//                       neighbouring output pixels, so cells shared by overlapping windows are
+//                       loaded, and taken through the element-wise operations, once per block.
+//   nhwc_pool_any_kernel  the same for any window, one output pixel per lane.
 //
 // The arithmetic and its order are those of the NCHW kernels (float32, BatchNorm one fused
 // multiply-add, window cells visited row-major, first maximum wins, the average's sum taken
@@ -111,16 +113,165 @@ __global__ __launch_bounds__(512) void nhwc_stream_kernel(const NhwcK k)
     }
 }
 
-// One pooling operation.  KH, KW > 0: the window is a compile-time constant, all its cells
-// are requested at once and the element-wise operations run once over all of them; KH == 0:
-// any window, one cell at a time.
-template <int DT, int VEC, int KH, int KW>
+// Work-groups are handed to the chip's 8 XCDs round-robin, and each XCD has its own L2.
+// Overlapping windows make neighbouring work-groups read the same input rows and columns;
+// with this remapping XCD x gets one contiguous eighth of the output and finds the shared
+// cells in its own L2 (measured: 8 % faster for 3x3/2 float32, 4 % slower for the disjoint
+// 2x2/2 windows, which therefore keep the plain order).  A bijection of [0, n): the last
+// n % 8 groups keep their index.
+BS_DEV uint32_t xcd_contiguous(uint32_t bid, uint32_t n)
+{
+    constexpr uint32_t X = 8;
+    const uint32_t per = n / X;
+    return bid >= per * X ? bid : (bid % X) * per + bid / X;
+}
+
+// What a lane adds to its running maximum / sum for one window cell.
+template <int VEC, bool IDX>
+BS_DEV void take_cell(bool is_max, const float (&v)[VEC], int32_t cell_index, float (&acc)[VEC], int32_t (&bi)[VEC])
+{
+    if (is_max) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            if constexpr (IDX) {
+                const bool g = v[e] > acc[e];
+                acc[e] = g ? v[e] : acc[e];
+                bi[e] = g ? cell_index : bi[e];
+            } else {
+                acc[e] = __builtin_fmaxf(acc[e], v[e]);  // the same value as the first maximum
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = acc[e] + v[e];
+    }
+}
+
+// float32 reciprocal of the average's divisor for the window at (h0, w0), in-range part
+// [hlo, hhi) x [wlo, whi)
+BS_DEV float avg_inv(const PoolK &p, int32_t kh, int32_t kw, int32_t H, int32_t W, int32_t h0, int32_t w0,
+                     int32_t hlo, int32_t hhi, int32_t wlo, int32_t whi)
+{
+    if (!p.count_include_pad) return 1.0f / (float)max((hhi - hlo) * (whi - wlo), 1);
+    if (p.count_include_pad == 2) {  // ceil mode: cells inside the padded plane
+        const int32_t nr = min(h0 + kh, H + p.ph) - h0, nc = min(w0 + kw, W + p.pw) - w0;
+        return 1.0f / (float)max(nr * nc, 1);
+    }
+    return p.inv_kk;
+}
+
+// One pooling operation with a compile-time window KH x KW and strides SH x SW.  A lane
+// produces VEC channels of a block of OHB x OWB neighbouring output pixels: the
+// ((OHB-1)*SH + KH) x ((OWB-1)*SW + KW) input cells under the block are requested at once,
+// the element-wise operations before the pool run once per cell (not once per window that
+// holds it), then every output of the block takes its window from the registers.
+// IDX: keep the argmax (only when an index output was asked for).
+template <int DT, int VEC, int KH, int KW, int SH, int SW, int OHB, int OWB, bool IDX>
 __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
+{
+    constexpr int CR = (OHB - 1) * SH + KH, CC = (OWB - 1) * SW + KW, NCELL = CR * CC, NOUT = OHB * OWB;
+    constexpr bool OVERLAP = KH > SH || KW > SW;
+    uint32_t i = (OVERLAP ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x) * blockDim.x + threadIdx.x;
+    const bool live = i < k.total;
+    i = live ? i : 0u;
+    // lane -> (image n, block row, block column, channel vector cv), cv fastest
+    const uint32_t blk = fdiv(i, k.div_cv);
+    const uint32_t c0 = (i - blk * k.div_cv.d) * VEC;
+    const uint32_t t = fdiv(blk, k.div_wo);
+    const int32_t ow0 = (int32_t)(blk - t * k.div_wo.d) * OWB;
+    const uint32_t n = fdiv(t, k.div_ho);
+    const int32_t oh0 = (int32_t)(t - n * k.div_ho.d) * OHB;
+    const PoolK &p = k.pool;
+    const int32_t hb = oh0 * SH - p.ph, wb = ow0 * SW - p.pw;  // plane position of cell (0, 0)
+    const uint32_t img = n * (uint32_t)(k.H * k.W);            // first pixel of the image
+    const bool is_max = p.kind == OP_MAXPOOL;
+    const bool interior = hb >= 0 && hb + CR <= k.H && wb >= 0 && wb + CC <= k.W;
+
+    float x[NCELL][VEC];
+    uint32_t off[NCELL];
+    {
+        Raw<DT, VEC> raw[NCELL];
+#pragma unroll
+        for (int r = 0; r < CR; ++r)
+#pragma unroll
+            for (int c = 0; c < CC; ++c) {
+                // a cell outside the plane is padding: requested from the nearest cell inside
+                // (a safe address) and never used
+                const int32_t ih = min(max(hb + r, 0), k.H - 1), iw = min(max(wb + c, 0), k.W - 1);
+                off[r * CC + c] = (img + (uint32_t)(ih * k.W + iw)) * (uint32_t)k.C + c0;
+                raw[r * CC + c] = load_raw<DT, VEC>(k.in, off[r * CC + c]);
+            }
+#pragma unroll
+        for (int cell = 0; cell < NCELL; ++cell) unpack<DT, VEC>(raw[cell], x[cell]);
+    }
+    apply_ew_nhwc<DT, VEC, NCELL>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
+
+    float y[NOUT][VEC];
+    int32_t yi[NOUT][VEC];
+    uint32_t ooff[NOUT];
+    bool oin[NOUT];
+#pragma unroll
+    for (int a = 0; a < OHB; ++a)
+#pragma unroll
+        for (int b = 0; b < OWB; ++b) {
+            const int o = a * OWB + b;
+            const int32_t oh = oh0 + a, ow = ow0 + b;
+            oin[o] = oh < k.Ho && ow < k.Wo;
+            // outputs beyond the plane's edge (ragged blocks) are computed at a safe address and dropped
+            ooff[o] = ((n * (uint32_t)k.Ho + (uint32_t)min(oh, k.Ho - 1)) * (uint32_t)k.Wo + (uint32_t)min(ow, k.Wo - 1)) *
+                          (uint32_t)k.C + c0;
+            const int32_t h0 = hb + a * SH, w0 = wb + b * SW;
+            const int32_t hlo = max(h0, 0), hhi = min(h0 + KH, k.H), wlo = max(w0, 0), whi = min(w0 + KW, k.W);
+            float acc[VEC];
+            int32_t bi[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                acc[e] = is_max ? -INFINITY : 0.0f;
+                bi[e] = hlo * k.W + wlo;  // first in-range cell
+            }
+            if (interior) {
+#pragma unroll
+                for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw)
+                        take_cell<VEC, IDX>(is_max, x[(a * SH + dh) * CC + b * SW + dw], (h0 + dh) * k.W + w0 + dw, acc, bi);
+            } else {
+#pragma unroll
+                for (int dh = 0; dh < KH; ++dh)
+#pragma unroll
+                    for (int dw = 0; dw < KW; ++dw)
+                        if (h0 + dh >= hlo && h0 + dh < hhi && w0 + dw >= wlo && w0 + dw < whi)
+                            take_cell<VEC, IDX>(is_max, x[(a * SH + dh) * CC + b * SW + dw], (h0 + dh) * k.W + w0 + dw, acc, bi);
+            }
+            if (is_max) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) y[o][e] = acc[e];
+            } else {
+                const float inv = avg_inv(p, KH, KW, k.H, k.W, h0, w0, hlo, hhi, wlo, whi);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) y[o][e] = round_store<DT>(acc[e] * inv);
+            }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) yi[o][e] = bi[e];
+        }
+    apply_ew_nhwc<DT, VEC, NOUT>(y, c0, ooff, k.post, k.n_post, k.params, k.C, k.res);
+#pragma unroll
+    for (int o = 0; o < NOUT; ++o)
+        if (live && oin[o]) {
+            store_elems<DT, VEC>(k.out, ooff[o], y[o]);
+            if constexpr (IDX) {
+                if (is_max) store_indices<VEC>(k.idx + ooff[o], yi[o]);
+            }
+        }
+}
+
+// Any window: one output pixel per lane, one cell at a time.
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void nhwc_pool_any_kernel(const NhwcK k)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     const bool live = i < k.total;
     i = live ? i : 0u;
-    // lane -> (image n, output row oh, output column ow, channel vector cv), cv fastest
     const uint32_t pix = fdiv(i, k.div_cv);
     const uint32_t c0 = (i - pix * k.div_cv.d) * VEC;
     const uint32_t t = fdiv(pix, k.div_wo);
@@ -128,84 +279,32 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
     const uint32_t n = fdiv(t, k.div_ho);
     const int32_t oh = (int32_t)(t - n * (uint32_t)k.Ho);
     const PoolK &p = k.pool;
-    const int32_t kh = KH > 0 ? KH : p.kh, kw = KH > 0 ? KW : p.kw;
     const int32_t h0 = oh * p.sh - p.ph, w0 = ow * p.sw - p.pw;
     // in-range part of the window; never empty (the padding is at most half the window)
-    const int32_t hlo = max(h0, 0), hhi = min(h0 + kh, k.H), wlo = max(w0, 0), whi = min(w0 + kw, k.W);
-    const uint32_t img = n * (uint32_t)(k.H * k.W);  // first pixel of the image
+    const int32_t hlo = max(h0, 0), hhi = min(h0 + p.kh, k.H), wlo = max(w0, 0), whi = min(w0 + p.kw, k.W);
+    const uint32_t img = n * (uint32_t)(k.H * k.W);
     const bool is_max = p.kind == OP_MAXPOOL;
-
     float acc[VEC];
     int32_t bi[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
         acc[e] = is_max ? -INFINITY : 0.0f;
-        bi[e] = hlo * k.W + wlo;  // first in-range cell
+        bi[e] = hlo * k.W + wlo;
     }
-    auto take = [&](const float (&v)[VEC], int32_t ih, int32_t iw) {
-        if (is_max) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const bool g = v[e] > acc[e];
-                acc[e] = g ? v[e] : acc[e];
-                bi[e] = g ? ih * k.W + iw : bi[e];
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] = acc[e] + v[e];
+    for (int32_t ih = hlo; ih < hhi; ++ih)
+        for (int32_t iw = wlo; iw < whi; ++iw) {
+            const uint32_t off1[1] = {(img + (uint32_t)(ih * k.W + iw)) * (uint32_t)k.C + c0};
+            float x[1][VEC];
+            unpack<DT, VEC>(load_raw<DT, VEC>(k.in, off1[0]), x[0]);
+            apply_ew_nhwc<DT, VEC, 1>(x, c0, off1, k.pre, k.n_pre, k.params, k.C, k.res);
+            take_cell<VEC, true>(is_max, x[0], ih * k.W + iw, acc, bi);
         }
-    };
-
-    if constexpr (KH > 0) {
-        constexpr int NCELL = KH * KW;
-        float x[NCELL][VEC];
-        uint32_t off[NCELL];
-        bool in[NCELL];
-        Raw<DT, VEC> raw[NCELL];
-#pragma unroll
-        for (int dh = 0; dh < KH; ++dh)
-#pragma unroll
-            for (int dw = 0; dw < KW; ++dw) {
-                const int32_t ih = h0 + dh, iw = w0 + dw;
-                const int cell = dh * KW + dw;
-                in[cell] = ih >= hlo && ih < hhi && iw >= wlo && iw < whi;
-                // a cell outside the plane is the pooling operation's padding: requested from a
-                // safe address (the first in-range cell) and never used
-                const int32_t ch = in[cell] ? ih : hlo, cw = in[cell] ? iw : wlo;
-                off[cell] = (img + (uint32_t)(ch * k.W + cw)) * (uint32_t)k.C + c0;
-                raw[cell] = load_raw<DT, VEC>(k.in, off[cell]);
-            }
-#pragma unroll
-        for (int cell = 0; cell < NCELL; ++cell) unpack<DT, VEC>(raw[cell], x[cell]);
-        apply_ew_nhwc<DT, VEC, NCELL>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
-#pragma unroll
-        for (int dh = 0; dh < KH; ++dh)
-#pragma unroll
-            for (int dw = 0; dw < KW; ++dw)
-                if (in[dh * KW + dw]) take(x[dh * KW + dw], h0 + dh, w0 + dw);
-    } else {
-        for (int32_t ih = hlo; ih < hhi; ++ih)
-            for (int32_t iw = wlo; iw < whi; ++iw) {
-                const uint32_t off1[1] = {(img + (uint32_t)(ih * k.W + iw)) * (uint32_t)k.C + c0};
-                float x[1][VEC];
-                unpack<DT, VEC>(load_raw<DT, VEC>(k.in, off1[0]), x[0]);
-                apply_ew_nhwc<DT, VEC, 1>(x, c0, off1, k.pre, k.n_pre, k.params, k.C, k.res);
-                take(x[0], ih, iw);
-            }
-    }
-
     float y[1][VEC];
     if (is_max) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) y[0][e] = acc[e];
     } else {
-        float inv = p.inv_kk;
-        if (!p.count_include_pad) {
-            inv = 1.0f / (float)((hhi - hlo) * (whi - wlo));
-        } else if (p.count_include_pad == 2) {  // ceil mode: cells inside the padded plane
-            const int32_t nr = min(h0 + kh, k.H + p.ph) - h0, nc = min(w0 + kw, k.W + p.pw) - w0;
-            inv = 1.0f / (float)max(nr * nc, 1);
-        }
+        const float inv = avg_inv(p, p.kh, p.kw, k.H, k.W, h0, w0, hlo, hhi, wlo, whi);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) y[0][e] = round_store<DT>(acc[e] * inv);
     }
@@ -217,18 +316,54 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
     }
 }
 
-template <int DT, int VEC>
-static void launch_nhwc_t(const NhwcK &k, dim3 grid, dim3 block, hipStream_t st)
+// Output block (rows x columns of output pixels per lane) of the compiled windows.  Measured on
+// MI355X: sharing cells between the outputs of a block pays for stride 1 (3x3/1: 2 x 2 outputs
+// from 4 x 4 cells with float32 vectors, 2 x 1 from 4 x 3 with the twice as long 16-bit
+// vectors), not for stride 2 (3x3/2: 1 x 2 was 20..60 % slower than 1 x 1: registers).
+// The planner sizes the grid with it, the launcher picks the instance.
+void nhwc_block(const PoolK &p, int32_t vec, int32_t dtype, int32_t &ohb, int32_t &owb)
 {
-    if (k.pool.kind == 0) {
-        nhwc_stream_kernel<DT, VEC, 4><<<grid, block, 0, st>>>(k);
-    } else if (k.pool.kh == 2 && k.pool.kw == 2) {
-        nhwc_pool_kernel<DT, VEC, 2, 2><<<grid, block, 0, st>>>(k);
-    } else if (k.pool.kh == 3 && k.pool.kw == 3) {
-        nhwc_pool_kernel<DT, VEC, 3, 3><<<grid, block, 0, st>>>(k);
-    } else {
-        nhwc_pool_kernel<DT, VEC, 0, 0><<<grid, block, 0, st>>>(k);
+    (void)dtype;
+    ohb = owb = 1;
+    if (p.kh == 3 && p.kw == 3 && p.sh == 1 && p.sw == 1) {
+        ohb = 2;
+        owb = vec <= 4 ? 2 : 1;
     }
+}
+
+template <int DT, int VEC, int KH, int KW, int SH, int SW, int OHB, int OWB>
+static void launch_block(const NhwcK &k, dim3 grid, dim3 block, hipStream_t st)
+{
+    if (k.idx && k.pool.kind == OP_MAXPOOL) nhwc_pool_kernel<DT, VEC, KH, KW, SH, SW, OHB, OWB, true><<<grid, block, 0, st>>>(k);
+    else nhwc_pool_kernel<DT, VEC, KH, KW, SH, SW, OHB, OWB, false><<<grid, block, 0, st>>>(k);
+}
+
+template <int DT, int VEC>
+static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 block, hipStream_t st)
+{
+    const PoolK &p = k.pool;
+    if (p.kind == 0) {
+        nhwc_stream_kernel<DT, VEC, 4><<<grid, block, 0, st>>>(k);
+        return BS_OK;
+    }
+    int32_t ohb, owb;
+    nhwc_block(p, VEC, dtype, ohb, owb);
+    // the plan's lane grid must be the one the kernel's block shape implies
+    if ((int32_t)k.div_wo.d != (k.Wo + owb - 1) / owb || (int32_t)k.div_ho.d != (k.Ho + ohb - 1) / ohb)
+        return BS_ERR_UNSUPPORTED;
+    constexpr bool WIDE = VEC <= 4;
+    if (p.kh == 2 && p.kw == 2 && p.sh == 2 && p.sw == 2) {
+        launch_block<DT, VEC, 2, 2, 2, 2, 1, 1>(k, grid, block, st);
+    } else if (p.kh == 3 && p.kw == 3 && p.sh == 2 && p.sw == 2) {
+        if (ohb != 1 || owb != 1) return BS_ERR_UNSUPPORTED;
+        launch_block<DT, VEC, 3, 3, 2, 2, 1, 1>(k, grid, block, st);
+    } else if (p.kh == 3 && p.kw == 3 && p.sh == 1 && p.sw == 1) {
+        if (ohb != 2 || owb != (WIDE ? 2 : 1)) return BS_ERR_UNSUPPORTED;
+        launch_block<DT, VEC, 3, 3, 1, 1, 2, WIDE ? 2 : 1>(k, grid, block, st);
+    } else {
+        nhwc_pool_any_kernel<DT, VEC><<<grid, block, 0, st>>>(k);
+    }
+    return BS_OK;
 }
 
 bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream)
@@ -239,19 +374,10 @@ bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, 
     // the vector width the plan was made for must be one the kernels exist for and must divide C
     if ((vec != 1 && vec != full) || k.C % vec != 0 || (int64_t)k.div_cv.d * vec != k.C) return BS_ERR_UNSUPPORTED;
     const dim3 g((uint32_t)grid), b((uint32_t)threads);
-    if (dtype == BS_F32) {
-        if (vec == 4) launch_nhwc_t<DT_F32, 4>(k, g, b, st);
-        else launch_nhwc_t<DT_F32, 1>(k, g, b, st);
-    } else if (dtype == BS_BF16) {
-        if (vec == 8) launch_nhwc_t<DT_BF16, 8>(k, g, b, st);
-        else launch_nhwc_t<DT_BF16, 1>(k, g, b, st);
-    } else if (dtype == BS_F16) {
-        if (vec == 8) launch_nhwc_t<DT_F16, 8>(k, g, b, st);
-        else launch_nhwc_t<DT_F16, 1>(k, g, b, st);
-    } else {
-        return BS_ERR_UNSUPPORTED;
-    }
-    return BS_OK;
+    if (dtype == BS_F32) return vec == 4 ? launch_nhwc_t<DT_F32, 4>(k, dtype, g, b, st) : launch_nhwc_t<DT_F32, 1>(k, dtype, g, b, st);
+    if (dtype == BS_BF16) return vec == 8 ? launch_nhwc_t<DT_BF16, 8>(k, dtype, g, b, st) : launch_nhwc_t<DT_BF16, 1>(k, dtype, g, b, st);
+    if (dtype == BS_F16) return vec == 8 ? launch_nhwc_t<DT_F16, 8>(k, dtype, g, b, st) : launch_nhwc_t<DT_F16, 1>(k, dtype, g, b, st);
+    return BS_ERR_UNSUPPORTED;
 }
 
 }  // namespace bs

@@ -436,22 +436,58 @@ static bs_status plan_nhwc(const bs_stack *s, Sequence &q)
         }
     }
     k.C = C;
+    // Maximum first.  Element-wise operations that never decrease when their input increases
+    // (BatchNorm with scales >= 0, ReLU, leaky ReLU with a slope >= 0, clamp; rounding to the
+    // storage type is of that kind too) commute with the maximum: max_i f(x_i) = f(max_i x_i),
+    // the same float32 value.  Only the sign of a zero could differ, and not once a ReLU has
+    // made every zero +0.  So when no argmax is wanted and the list before a max pool is of
+    // that kind and holds a ReLU, the pool runs on the raw input and the list on its output:
+    // once per output instead of once per window cell.
+    if (seen && k.pool.kind == OP_MAXPOOL && k.pool.idx_slot < 0 && k.n_pre > 0 && k.n_pre + k.n_post <= K_MAX_EW) {
+        bool monotone = true, relu = false;
+        for (int32_t j = 0; j < k.n_pre && monotone; ++j) {
+            const EwOp &e = k.pre[j];
+            if (e.kind == OP_BN) {
+                for (int32_t c = 0; c < C; ++c) monotone = monotone && s->host_params[(size_t)e.arg + c] >= 0.0f;
+            } else if (e.kind == OP_LEAKY) {
+                monotone = s->host_params[(size_t)e.arg] >= 0.0f;
+            } else if (e.kind == OP_RELU) {
+                relu = true;
+            } else if (e.kind != OP_CLAMP) {
+                monotone = false;  // a residual Add differs from cell to cell
+            }
+        }
+        if (monotone && relu) {
+            EwOp moved[K_MAX_EW];
+            int32_t m = 0;
+            for (int32_t j = 0; j < k.n_pre; ++j) moved[m++] = k.pre[j];
+            for (int32_t j = 0; j < k.n_post; ++j) moved[m++] = k.post[j];
+            for (int32_t j = 0; j < m; ++j) k.post[j] = moved[j];
+            k.n_post = m;
+            k.n_pre = 0;
+        }
+    }
     if (!seen) {
         k.H = k.Ho = (int32_t)q.in_shape[2];
         k.W = k.Wo = (int32_t)q.in_shape[3];
     }
     q.variant = seen ? BS_VARIANT_NHWC_POOL : BS_VARIANT_NHWC_STREAM;
-    const int64_t pixels = q.in_shape[0] * (int64_t)k.Ho * k.Wo;
-    k.total = (uint32_t)(pixels * (C / vec));
+    // a lane takes one channel vector of a block of ohb x owb output pixels (1 x 1: one pixel)
+    int32_t ohb = 1, owb = 1;
+    if (seen) nhwc_block(k.pool, vec, s->dtype, ohb, owb);
+    const int32_t bh = (k.Ho + ohb - 1) / ohb, bw = (k.Wo + owb - 1) / owb;
+    k.total = (uint32_t)(q.in_shape[0] * (int64_t)bh * bw * (C / vec));
     k.div_cv = make_fastdiv((uint32_t)(C / vec));
-    k.div_wo = make_fastdiv((uint32_t)k.Wo);
-    k.div_ho = make_fastdiv((uint32_t)k.Ho);
+    k.div_wo = make_fastdiv((uint32_t)bw);
+    k.div_ho = make_fastdiv((uint32_t)bh);
+    q.tile_rows = ohb;
+    q.tile_cols = owb;
     q.threads = std::min(q.threads, 256);
     const int64_t per_group = (int64_t)q.threads * (seen ? 1 : K_STREAM_U);
     q.grid = ((int64_t)k.total + per_group - 1) / per_group;
     q.lds_bytes = 0;
-    q.redundancy = seen ? (double)k.Ho * k.pool.kh * k.Wo * k.pool.kw / ((double)k.H * k.W) : 1.0;
-    q.tile_rows = q.tile_cols = 0;
+    q.redundancy = !seen ? 1.0 : (double)bh * ((ohb - 1) * k.pool.sh + k.pool.kh) * bw * ((owb - 1) * k.pool.sw + k.pool.kw) /
+                                      ((double)k.H * k.W);
     q.planes_per_group = 0;
     q.n_levels = seen ? 1 : 0;
     return BS_OK;

@@ -689,6 +689,43 @@ def test_channels_last_configs_reduced_batch(name, dtype):
     _check_nhwc(layers, x, res, dtype, name)
 
 
+def _premax_stacks(c):
+    """Max pools without an index output behind lists that never decrease (the pool may then
+    run first), and lists that do not qualify (a negative scale or slope, no ReLU, an Add)."""
+    neg = wl.bn_params(c, 131)
+    neg["gamma"] = neg["gamma"].copy()
+    neg["gamma"][::2] *= -1.0
+    zero = wl.bn_params(c, 132)
+    zero["beta"] = np.zeros(c, np.float32)
+    zero["mean"] = np.zeros(c, np.float32)
+    return {
+        "bn_relu_max3s2": [wl.bn_params(c, 130), wl.relu(), wl.maxpool(3, 2, 1)],
+        "bn_relu_max2": [wl.bn_params(c, 130), wl.relu(), wl.maxpool(2, 2)],
+        "negative_scales": [neg, wl.relu(), wl.maxpool(3, 2, 1)],
+        "zero_shift": [zero, wl.relu(), wl.maxpool(3, 1, 1), wl.bn_params(c, 133)],
+        "long_list": [wl.relu(), wl.bn_params(c, 134), wl.leaky_relu(0.1), wl.clamp(-0.5, 2.0), wl.maxpool(2, 2),
+                      wl.bn_params(c, 135), wl.relu()],
+        "negative_slope": [wl.relu(), wl.bn_params(c, 136), wl.leaky_relu(-0.1), wl.maxpool(2, 2)],
+        "no_relu": [wl.bn_params(c, 137), wl.maxpool(3, 2, 1)],
+        "add_before": [wl.bn_params(c, 138), wl.add(), wl.relu(), wl.maxpool(2, 2)],
+        "any_window": [wl.bn_params(c, 139), wl.relu(), wl.maxpool((2, 3), (1, 2), (1, 1))],
+    }
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 13, 11), (1, 16, 12, 16), (2, 5, 9, 10)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_channels_last_max_pool_before_monotone_lists(shape, dtype):
+    """The planner lets a max pool without index output run before a list of element-wise
+    operations that never decrease; the values must stay those of the layer order, bit for
+    bit, zeros of both signs in the input included."""
+    for name, layers in _premax_stacks(shape[1]).items():
+        x = wl.activation(shape, 140, dtype)
+        x[:, :, ::3, ::2] = 0.0
+        x[:, :, 1::3, 1::2] = -0.0
+        res = [wl.activation(sh, 141 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
+        _check_nhwc(layers, x, res, dtype, f"premax/{name}{shape}")
+
+
 def test_channels_last_argument_checks():
     layers = [wl.bn_params(8, 3), wl.relu(), wl.maxpool(2, 2, 0, True)]
     x = wl.activation((2, 8, 6, 8), 120)
