@@ -476,13 +476,17 @@ def main():
                 for idx in ([False, True] if any(l["kind"] == "maxpool" for l in wl.build(name)[0]) else [False]):
                     sb = StackBench(name, dt, indices=idx)
                     m, p, mn = time_steps([sb], "fused", args.steps, args.warmup)
-                    ml, pl, _ = time_steps([sb], "lbl", max(10, args.steps // 4), 2)
+                    pl = {name: float("nan")}
+                    if not args.no_baseline:
+                        ml, pl, _ = time_steps([sb], "lbl", max(10, args.steps // 4), 2)
                     g = sb.bytes / (p[name] * 1e-3) / 1e9
                     row = {"config": name + ("+idx" if idx else ""), "dtype": dt,
                            "variant": sb.info["sequences"][0]["variant_name"], "MB": sb.bytes / 1e6,
                            "us_mean": p[name] * 1e3, "us_min": mn[name] * 1e3, "GBps": g,
                            "pct_peak": 100 * g / HBM_PEAK_GBPS, "img_s": sb.images / (p[name] * 1e-3),
-                           "lbl_us": pl[name] * 1e3, "speedup": pl[name] / p[name]}
+                           "lbl_us": pl[name] * 1e3, "speedup": pl[name] / p[name],
+                           # work-items per launch of every sequence: what a kernel trace lists as grid size
+                           "work_items": [q["grid"] * q["threads_per_group"] for q in sb.info["sequences"]]}
                     rows.append(row)
                     log(f"{row['config']:<16}{dt:<6}{row['variant']:<13}{row['MB']:>8.1f}{row['us_mean']:>9.1f}"
                         f"{row['us_min']:>8.1f}{g:>8.0f}{row['pct_peak']:>7.1f}{row['img_s']:>10.0f}"
