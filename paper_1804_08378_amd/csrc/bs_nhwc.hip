@@ -113,19 +113,6 @@ __global__ __launch_bounds__(512) void nhwc_stream_kernel(const NhwcK k)
     }
 }
 
-// Work-groups are handed to the chip's 8 XCDs round-robin, and each XCD has its own L2.
-// Overlapping windows make neighbouring work-groups read the same input rows and columns;
-// with this remapping XCD x gets one contiguous eighth of the output and finds the shared
-// cells in its own L2 (measured: 8 % faster for 3x3/2 float32, 4 % slower for the disjoint
-// 2x2/2 windows, which therefore keep the plain order).  A bijection of [0, n): the last
-// n % 8 groups keep their index.
-BS_DEV uint32_t xcd_contiguous(uint32_t bid, uint32_t n)
-{
-    constexpr uint32_t X = 8;
-    const uint32_t per = n / X;
-    return bid >= per * X ? bid : (bid % X) * per + bid / X;
-}
-
 // What a lane adds to its running maximum / sum for one window cell.
 template <int VEC, bool IDX>
 BS_DEV void take_cell(bool is_max, const float (&v)[VEC], int32_t cell_index, float (&acc)[VEC], int32_t (&bi)[VEC])
