@@ -69,8 +69,8 @@ class StackBench:
         self.cursor = 0
         self.info = self.fused.info()
 
-    def launch(self, which="fused", stream=None):
-        s = self.cursor
+    def launch(self, which="fused", stream=None, hot=False):
+        s = 0 if hot else self.cursor  # hot: always the same buffers (served by the last-level cache)
         self.cursor = (self.cursor + 1) % self.sets
         st = self.fused if which == "fused" else self.lbl
         st.run(self.x[s], self.res[s], out=self.out[s], indices=self.idx[s],
@@ -114,18 +114,19 @@ def time_steps(stacks, which, steps, warmup, streams=None):
     return (t1 - t0) * 1e3 / steps, per, mins
 
 
-def time_back_to_back(sb, which, launches):
+def time_back_to_back(sb, which, launches, hot=False):
     """Average duration of one launch of `sb` when `launches` of them run back to back between
-    one HIP event pair: the kernel's own duration plus the gap to the next launch."""
+    one HIP event pair: the kernel's own duration plus the gap to the next launch.  `hot`: every
+    launch on the same buffers instead of rotating ones."""
     import torch
 
     for _ in range(3):
-        sb.launch(which)
+        sb.launch(which, hot=hot)
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for _ in range(launches):
-        sb.launch(which)
+        sb.launch(which, hot=hot)
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) / launches
@@ -469,7 +470,7 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
         log(f"{'config':<16}{'dtype':<6}{'variant':<13}{'MB':>8}{'us mean':>9}{'us min':>8}{'GB/s':>8}"
-            f"{'%peak':>7}{'img/s':>10}{'lbl us':>9}{'speedup':>8}")
+            f"{'%peak':>7}{'img/s':>10}{'lbl us':>9}{'speedup':>8}{'b2b us':>8}{'hot us':>8}")
         rows = []
         for name in wl.CONFIG_NAMES:
             for dt in wl.build(name)[2]:
@@ -485,12 +486,18 @@ def main():
                            "us_mean": p[name] * 1e3, "us_min": mn[name] * 1e3, "GBps": g,
                            "pct_peak": 100 * g / HBM_PEAK_GBPS, "img_s": sb.images / (p[name] * 1e-3),
                            "lbl_us": pl[name] * 1e3, "speedup": pl[name] / p[name],
+                           # back-to-back launches over rotating buffers, and on one buffer set: the
+                           # latter is served by the 256 MB last-level cache where the tensors fit
+                           # and is no HBM figure
+                           "us_back_to_back": time_back_to_back(sb, "fused", args.steps) * 1e3,
+                           "us_hot_single_buffer": time_back_to_back(sb, "fused", args.steps, hot=True) * 1e3,
                            # work-items per launch of every sequence: what a kernel trace lists as grid size
                            "work_items": [q["grid"] * q["threads_per_group"] for q in sb.info["sequences"]]}
                     rows.append(row)
                     log(f"{row['config']:<16}{dt:<6}{row['variant']:<13}{row['MB']:>8.1f}{row['us_mean']:>9.1f}"
                         f"{row['us_min']:>8.1f}{g:>8.0f}{row['pct_peak']:>7.1f}{row['img_s']:>10.0f}"
-                        f"{row['lbl_us']:>9.1f}{row['speedup']:>8.2f}")
+                        f"{row['lbl_us']:>9.1f}{row['speedup']:>8.2f}{row['us_back_to_back']:>8.1f}"
+                        f"{row['us_hot_single_buffer']:>8.1f}")
                     del sb
                     torch.cuda.empty_cache()
         out["all_configs"] = rows
