@@ -215,82 +215,59 @@ def frontend_stacks(names=("vgg_a", "vgg_b", "vgg_c"), batch=32, reps=50):
             "optimizable_layers_speedup": round(tot_ref / tot_opt, 2)}
 
 
-def frontend_network(batch=32, reps=10):
-    """A whole residual network with hand-written forward methods (18 layers, basic blocks of
-    two 3x3 convolutions, 64..512 channels, 224 x 224 input: the published ResNet-18 shape, random
-    weights), run by PyTorch eager and after `frontend.optimize_graph`: convolutions stay in
-    PyTorch on both sides, every BatchNorm / ReLU / Add / pooling chain becomes one stack call.
-    The kind of figure Sections 5.2-5.4 report (speed-up of the whole network)."""
+def frontend_network(batch=32, reps=10, names=("vgg16_bn", "resnet18", "resnet50", "densenet121"),
+                     dtypes=("float32", "float16"), channels_last=False):
+    """Whole networks of the families Sections 5.2-5.4 evaluate (architectures written from their
+    published descriptions in `paper_1804_08378_amd/zoo.py`, hand-written forward methods, random
+    weights, 3 x 224 x 224 inputs), forward pass by PyTorch eager and after
+    `frontend.optimize_graph`: convolutions and fully connected layers stay in PyTorch on both
+    sides, every chain of BatchNorm / ReLU / Add / pooling operations becomes one stack call.
+    `stacks` / `optimizable` are what the paper's detail table calls Stacks / Opt."""
     import torch
-    import torch.nn.functional as F
-    from torch import nn
     from paper_1804_08378_amd import frontend as fe
+    from paper_1804_08378_amd import zoo
 
-    class Block(nn.Module):
-        def __init__(self, cin, cout, stride):
-            super().__init__()
-            self.conv1 = nn.Conv2d(cin, cout, 3, stride, 1, bias=False)
-            self.bn1 = nn.BatchNorm2d(cout)
-            self.conv2 = nn.Conv2d(cout, cout, 3, 1, 1, bias=False)
-            self.bn2 = nn.BatchNorm2d(cout)
-            self.down = None
-            if stride != 1 or cin != cout:
-                self.down = nn.Sequential(nn.Conv2d(cin, cout, 1, stride, bias=False), nn.BatchNorm2d(cout))
-
-        def forward(self, x):
-            out = F.relu(self.bn1(self.conv1(x)))
-            out = self.bn2(self.conv2(out))
-            return F.relu(out + (x if self.down is None else self.down(x)))
-
-    class Net(nn.Module):
-        def __init__(self):
-            super().__init__()
-            self.conv = nn.Conv2d(3, 64, 7, 2, 3, bias=False)
-            self.bn = nn.BatchNorm2d(64)
-            self.pool = nn.MaxPool2d(3, 2, 1)
-            blocks, cin = [], 64
-            for cout, stride in ((64, 1), (64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2), (512, 1)):
-                blocks.append(Block(cin, cout, stride))
-                cin = cout
-            self.blocks = nn.Sequential(*blocks)
-            self.fc = nn.Linear(512, 1000)
-
-        def forward(self, x):
-            x = self.blocks(self.pool(F.relu(self.bn(self.conv(x)))))
-            return self.fc(torch.flatten(F.adaptive_avg_pool2d(x, 1), 1))
-
-    torch.manual_seed(0)
+    make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "vgg11_bn": lambda: zoo.vgg_bn(11), "resnet18": lambda: zoo.resnet(18),
+            "resnet50": lambda: zoo.resnet(50), "densenet121": lambda: zoo.densenet(121)}
     rows = []
-    log(f"{'dtype':<8}{'torch eager ms':>16}{'optimized ms':>14}{'speed-up':>10}{'stacks':>8}")
-    for dtype in (torch.float32, torch.float16):
-        ref = Net().cuda().eval().to(dtype)
-        opt = fe.optimize_graph(ref)
-        xs = [torch.randn(batch, 3, 224, 224, device="cuda").to(dtype) for _ in range(2)]
-        t = {}
-        with torch.no_grad():
-            a, b = ref(xs[0]).float(), opt(xs[0]).float()
-            diff = float((a - b).abs().max() / a.abs().max().clamp_min(1e-30))
-            for key, mod in (("ref", ref), ("opt", opt)):
-                for i in range(3):
-                    mod(xs[i % 2])
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in range(reps):
-                    mod(xs[i % 2])
-                e1.record()
-                torch.cuda.synchronize()
-                t[key] = e0.elapsed_time(e1) / reps
-        name = str(dtype).replace("torch.", "")
-        rows.append({"dtype": name, "torch_eager_ms": round(t["ref"], 3), "optimized_ms": round(t["opt"], 3),
-                     "speedup": round(t["ref"] / t["opt"], 3), "stacks": len(opt.optimized_stacks),
-                     "max_rel_diff_vs_torch": diff})
-        log(f"{name:<8}{t['ref']:>16.3f}{t['opt']:>14.3f}{t['ref'] / t['opt']:>10.3f}{len(opt.optimized_stacks):>8}")
-        for st in opt.optimized_stacks:
-            st.close()
-        del ref, opt, xs
-    return {"what": "18-layer residual network (hand-written forward), batch %d, 3x224x224, whole forward pass" % batch,
-            "rows": rows}
+    log(f"{'network':<14}{'dtype':<9}{'stacks':>7}{'opt.':>6}{'torch eager ms':>16}{'optimized ms':>14}{'speed-up %':>12}")
+    for name in names:
+        for dname in dtypes:
+            dtype = getattr(torch, dname)
+            torch.manual_seed(0)
+            ref = zoo.randomize_batchnorm(make[name]()).cuda().eval().to(dtype)
+            xs = [torch.randn(batch, 3, 224, 224, device="cuda").to(dtype) for _ in range(2)]
+            if channels_last:
+                ref = ref.to(memory_format=torch.channels_last)
+                xs = [x.contiguous(memory_format=torch.channels_last) for x in xs]
+            opt = fe.optimize_graph(ref)
+            t = {}
+            with torch.no_grad():
+                a, b = ref(xs[0]).float(), opt(xs[0]).float()
+                diff = float((a - b).abs().max() / a.abs().max().clamp_min(1e-30))
+                for key, mod in (("ref", ref), ("opt", opt)):
+                    for i in range(3):
+                        mod(xs[i % 2])
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for i in range(reps):
+                        mod(xs[i % 2])
+                    e1.record()
+                    torch.cuda.synchronize()
+                    t[key] = e0.elapsed_time(e1) / reps
+            n_opt = sum(len(st.replaced) for st in opt.optimized_stacks)
+            rows.append({"network": name, "dtype": dname, "stacks": len(opt.optimized_stacks), "optimizable": n_opt,
+                         "torch_eager_ms": round(t["ref"], 3), "optimized_ms": round(t["opt"], 3),
+                         "speedup_pct": round(100 * (t["ref"] / t["opt"] - 1), 1), "max_rel_diff_vs_torch": diff})
+            log(f"{name:<14}{dname:<9}{len(opt.optimized_stacks):>7}{n_opt:>6}{t['ref']:>16.3f}{t['opt']:>14.3f}"
+                f"{100 * (t['ref'] / t['opt'] - 1):>12.1f}")
+            for st in opt.optimized_stacks:
+                st.close()
+            del ref, opt, xs
+            torch.cuda.empty_cache()
+    return {"what": "whole forward pass, batch %d, 3x224x224, %s, PyTorch eager vs optimize_graph"
+                    % (batch, "channels_last" if channels_last else "NCHW"), "rows": rows}
 
 
 def deep_stacks(shape=(64, 64, 56, 56), counts=(1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 40)):
@@ -355,11 +332,13 @@ def main():
     ap.add_argument("--streams", action="store_true",
                     help="enqueue the three independent stacks of a step on one HIP stream each (default priority) "
                          "instead of all on one stream: kernels then overlap at their edges")
+    ap.add_argument("--networks", action="store_true",
+                    help="also time whole VGG / ResNet / DenseNet forward passes: PyTorch eager against "
+                         "frontend.optimize_graph()")
     ap.add_argument("--nhwc", action="store_true",
                     help="also time every configuration with channels-last (NHWC) tensors and plans")
     ap.add_argument("--frontend", action="store_true",
-                    help="also time the VGG stacks as torch modules, and a whole residual network with hand-written "
-                         "forward methods: PyTorch eager against frontend.optimize() / optimize_graph()")
+                    help="also time the VGG stacks as torch modules: PyTorch eager against frontend.optimize()")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
                     help="counter probe for rocprofv3 --pmc: N launches of a plain copy of known size, "
                          "then N launches of each VGG stack; no timing, no JSON")
@@ -448,7 +427,9 @@ def main():
         out["deep_stacks"] = deep_stacks()
     if args.frontend:
         out["frontend"] = frontend_stacks()
-        out["frontend_network"] = frontend_network()
+    if args.networks:
+        out["networks"] = frontend_network()
+        out["networks_channels_last"] = frontend_network(dtypes=("float16",), channels_last=True)
 
     if args.all:
         del stacks

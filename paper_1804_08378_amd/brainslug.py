@@ -378,6 +378,7 @@ class Stack:
         self.n_idx = bs_stack_num_index_outputs(self.handle)
         self._workspace = None
         self._workspace_bytes = 0
+        self._fast = None
         self.layout = BS_LAYOUT_NCHW
 
     def close(self):
@@ -391,6 +392,7 @@ class Stack:
         bs_stack_plan(self.handle, **opts)
         self.layout = int(opts.get("layout", BS_LAYOUT_NCHW))
         self._workspace = None
+        self._fast = None
         self._workspace_bytes = bs_stack_workspace_bytes(self.handle)
         return self
 
@@ -453,6 +455,29 @@ class Stack:
             bs_stack_run_strided(self.handle, x.data_ptr(), batch_stride(x), res, out.data_ptr(),
                                  batch_stride(out), idx, wsp, wsn, st)
         return out, indices
+
+    def run_unchecked(self, x, residuals, out):
+        """`bs_stack_run` on dense tensors of the plan's layout with as little Python in the way
+        as possible (no index outputs): for callers that have validated shapes, dtypes and
+        layouts themselves -- the front-end does, once per call.  The library still checks
+        alignment, aliasing and the workspace."""
+        import torch
+        fast = self._fast
+        if fast is None:
+            lib = load()
+            n = self._workspace_bytes
+            ws = self.workspace(x.device)
+            fast = self._fast = (lib.bs_stack_run, C.c_void_p(self.handle),
+                                 (C.c_void_p * max(1, self.n_res))(), ws.data_ptr() if ws is not None else None, n,
+                                 getattr(torch._C, "_cuda_getCurrentRawStream", None), x.device.index)
+        fn, h, res, wsp, wsn, raw_stream, dev = fast
+        for i, r in enumerate(residuals):
+            res[i] = r.data_ptr()
+        st = raw_stream(dev) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        rc = fn(h, x.data_ptr(), res, out.data_ptr(), None, wsp, wsn, st)
+        if rc != 0:
+            _check(rc, "bs_stack_run")
+        return out
 
     def _run_nhwc(self, x, residuals, out, indices, stream):
         """A channels-last plan: every tensor is in torch's channels_last memory format."""

@@ -186,15 +186,24 @@ class BrainSlugStack(nn.Module):
         """`residuals`: the second operand of every Add layer of the stack, in layer order."""
         if self.training:
             raise RuntimeError("BrainSlugStack implements the inference forward pass only: call model.eval()")
-        if not x.is_cuda or x.dim() != 4:
-            raise RuntimeError("BrainSlugStack needs a 4-D NCHW tensor on the GPU")
+        if not x.is_cuda:
+            raise RuntimeError("BrainSlugStack needs a tensor on the GPU")
+        if x.dim() != 4:
+            # the activations between fully connected layers: element-wise layers without
+            # per-channel parameters do not care about the shape, so the tensor runs as one row
+            if any(l["kind"] not in ("relu", "leaky_relu", "clamp", "add") for l in self.layers):
+                raise RuntimeError("BrainSlugStack needs a 4-D NCHW tensor for BatchNorm and pooling layers")
+            if any(tuple(r.shape) != tuple(x.shape) for r in residuals):
+                raise RuntimeError("residual operands must have the input's shape (no broadcasting)")
+            flat = self.forward(x.contiguous().view(1, 1, 1, -1), *[r.contiguous().view(1, 1, 1, -1) for r in residuals])
+            return flat.view(x.shape)
         if self.channels is not None and x.shape[1] != self.channels:
             raise RuntimeError(f"expected {self.channels} channels, got {x.shape[1]}")
         with torch.no_grad():
             # a channels_last tensor stays channels_last: the stack is planned for that memory
             # order and its output is channels_last as well (what the convolutions around it use)
             nhwc = not x.is_contiguous() and x.is_contiguous(memory_format=torch.channels_last)
-            st = self.plan_for(x.shape, x.dtype, nhwc)
+            st = self._plans.get((x.shape, x.dtype, nhwc)) or self.plan_for(x.shape, x.dtype, nhwc)
             mf = torch.channels_last if nhwc else torch.contiguous_format
             # a channel slice of a concatenation buffer is read in place; other layouts are copied
             if not nhwc and (bs.batch_stride(x) is None or (x.data_ptr() % 16) or
@@ -204,11 +213,16 @@ class BrainSlugStack(nn.Module):
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
             res = []
             for r, want in zip(residuals, st.res_shapes):
-                if tuple(r.shape) != tuple(want) or r.dtype != x.dtype or r.device != x.device:
+                if r.shape != want or r.dtype != x.dtype or r.device != x.device:
                     raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
                                        f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
                 res.append(r.contiguous(memory_format=mf))
-            out, _ = st.run(x, res, indices=[])
+            if x.is_contiguous(memory_format=mf):
+                # the common case: dense tensors of the plan's layout, validated above
+                out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf)
+                st.run_unchecked(x, res, out)
+            else:
+                out, _ = st.run(x, res, indices=[])
         return out
 
     def close(self) -> None:

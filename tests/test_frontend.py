@@ -17,6 +17,7 @@ from torch import nn
 from oracle import breadth_first as bf
 from paper_1804_08378_amd import brainslug as bs
 from paper_1804_08378_amd import frontend as fe
+from paper_1804_08378_amd import zoo
 
 
 def vgg_like(c_in=3, width=8, seed=0):
@@ -291,6 +292,56 @@ def test_chain_descriptions_reproduce_the_torch_model(name):
         assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(want).max()), ch.names
 
 
+# ------------------------------------------------------------------ the evaluated architectures
+ZOO = {"vgg16_bn": lambda: zoo.vgg_bn(16, 0.125, 10), "resnet18": lambda: zoo.resnet(18, 0.125, 10),
+       "resnet50": lambda: zoo.resnet(50, 0.125, 10), "densenet121": lambda: zoo.densenet(121, 0.25, 10)}
+
+
+def test_stack_counts_of_the_evaluated_architectures():
+    """Number of stacks found in the architectures of Section 5 (their structure does not depend
+    on the width).  The paper's detail table lists 15 stacks for VGG-16-BN and 124 stacks with
+    247 optimizable layers for DenseNet-121; residual networks come out one or two stacks lower
+    here because a block's closing ReLU and a following pool or the network's global average
+    pool are one chain."""
+    torch.manual_seed(0)
+    got = {}
+    for name, make in ZOO.items():
+        g = fe.optimize_graph(make().eval())
+        got[name] = (len(g.optimized_stacks), sum(len(s.replaced) for s in g.optimized_stacks))
+    assert got == {"vgg16_bn": (15, 36), "resnet18": (20, 47), "resnet50": (53, 120), "densenet121": (124, 247)}
+
+
+@pytest.mark.parametrize("name", ["vgg16_bn", "resnet50", "densenet121"])
+def test_zoo_chain_descriptions_reproduce_the_torch_model(name):
+    from torch import fx
+
+    torch.manual_seed(1)
+    model = zoo.randomize_batchnorm(ZOO[name](), 3).eval()
+    gm = fx.symbolic_trace(model)
+    values = {}
+
+    class Recorder(fx.Interpreter):
+        def run_node(self, n):
+            v = super().run_node(n)
+            values[n] = v.clone() if isinstance(v, torch.Tensor) else v
+            return v
+
+    with torch.no_grad():
+        size = 224 if name.startswith("vgg") else 64  # VGG's adaptive pool needs a 7 x 7 (or 14 x 14 ...) plane
+        Recorder(gm).run(torch.randn(1, 3, size, size, generator=torch.Generator().manual_seed(2)))
+    chains = fe.find_chains(gm)
+    for ch in chains[::3]:  # every third chain keeps the test short
+        xin = values[ch.source].numpy()
+        res = [values[r].numpy() for r in ch.residuals]
+        if xin.ndim != 4:  # activations between fully connected layers run as one row
+            xin = xin.reshape(1, 1, 1, -1)
+            res = [r.reshape(1, 1, 1, -1) for r in res]
+        layers = fe.resolve_layers([l for l in ch.layers if l], xin.shape)
+        got, _, _ = bf.run_stack(layers, np.ascontiguousarray(xin), res)
+        want = values[ch.nodes[-1]].numpy()
+        assert np.abs(got.reshape(want.shape) - want).max() <= 1e-5 * max(1.0, np.abs(want).max()), ch.names
+
+
 class Hazards(nn.Module):
     def __init__(self):
         super().__init__()
@@ -367,6 +418,32 @@ def test_graph_rewritten_model_matches_the_original_and_the_oracle(name, dtype):
         assert np.array_equal(out.float().cpu().numpy().view(np.uint32), expect.view(np.uint32)), stack.replaced
     for s in opt.optimized_stacks:
         s.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", list(ZOO))
+@pytest.mark.parametrize("channels_last", [False, True])
+def test_evaluated_architectures_rewritten_match_the_original(name, channels_last):
+    """Small versions of the paper's network families, float32: the rewritten graph gives the
+    original model's result (the activations between the fully connected layers of VGG run
+    through the library as well), also with channels_last tensors."""
+    torch.manual_seed(4)
+    ref = zoo.randomize_batchnorm(ZOO[name](), 5).eval().cuda()
+    size = 224 if name.startswith("vgg") else 64
+    x = torch.randn(2, 3, size, size, device="cuda")
+    if channels_last:
+        ref = ref.to(memory_format=torch.channels_last)
+        x = x.contiguous(memory_format=torch.channels_last)
+    opt = fe.optimize_graph(ref)
+    with torch.no_grad():
+        want, got = ref(x), opt(x)
+    assert (got - want).abs().max().item() <= 2e-4 * max(1.0, want.abs().max().item())
+    used = set()
+    for s in opt.optimized_stacks:
+        for st in s._plans.values():
+            used.update(q["variant_name"] for q in st.info()["sequences"])
+        s.close()
+    assert used and (not channels_last or any(v.startswith("nhwc") for v in used))
 
 
 @pytest.mark.gpu
