@@ -230,7 +230,8 @@ def frontend_network(batch=32, reps=10, names=("vgg16_bn", "resnet18", "resnet50
     make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "vgg11_bn": lambda: zoo.vgg_bn(11), "resnet18": lambda: zoo.resnet(18),
             "resnet50": lambda: zoo.resnet(50), "densenet121": lambda: zoo.densenet(121)}
     rows = []
-    log(f"{'network':<14}{'dtype':<9}{'stacks':>7}{'opt.':>6}{'torch eager ms':>16}{'optimized ms':>14}{'speed-up %':>12}")
+    log(f"{'network':<14}{'dtype':<9}{'stacks':>7}{'opt.':>6}{'torch eager ms':>16}{'optimized ms':>14}{'speed-up %':>12}"
+        f"{'graph torch':>12}{'graph opt.':>12}{'speed-up %':>12}")
     for name in names:
         for dname in dtypes:
             dtype = getattr(torch, dname)
@@ -256,12 +257,49 @@ def frontend_network(batch=32, reps=10, names=("vgg16_bn", "resnet18", "resnet50
                     e1.record()
                     torch.cuda.synchronize()
                     t[key] = e0.elapsed_time(e1) / reps
+            # the same two models captured in HIP graphs (torch.cuda.CUDAGraph): no launch overhead
+            # on either side.  Every replay is checked against the eager result, with eager work
+            # between the replays (convolutions are not bit-reproducible from run to run, so the
+            # check is a tolerance); a model whose replays disagree is reported as None.
+            tg = {}
+            for key, mod in (("ref", ref), ("opt", opt)):
+                with torch.no_grad():
+                    want = mod(xs[0]).float()
+                    side = torch.cuda.Stream()
+                    side.wait_stream(torch.cuda.current_stream())
+                    with torch.cuda.stream(side):
+                        for _ in range(2):
+                            mod(xs[0])
+                    torch.cuda.current_stream().wait_stream(side)
+                    torch.cuda.synchronize()
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph):
+                        y = mod(xs[0])
+                    good = True
+                    for _ in range(3):
+                        graph.replay()
+                        torch.cuda.synchronize()
+                        good = good and float((y.float() - want).abs().max() / want.abs().max().clamp_min(1e-30)) < 2e-3
+                        mod(xs[1])  # eager work between the replays
+                        torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(reps):
+                        graph.replay()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    tg[key] = e0.elapsed_time(e1) / reps if good else None
+                    del graph, y
             n_opt = sum(len(st.replaced) for st in opt.optimized_stacks)
+            both = tg["ref"] is not None and tg["opt"] is not None
             rows.append({"network": name, "dtype": dname, "stacks": len(opt.optimized_stacks), "optimizable": n_opt,
                          "torch_eager_ms": round(t["ref"], 3), "optimized_ms": round(t["opt"], 3),
-                         "speedup_pct": round(100 * (t["ref"] / t["opt"] - 1), 1), "max_rel_diff_vs_torch": diff})
+                         "speedup_pct": round(100 * (t["ref"] / t["opt"] - 1), 1), "max_rel_diff_vs_torch": diff,
+                         "graph_torch_ms": tg["ref"] and round(tg["ref"], 3), "graph_optimized_ms": tg["opt"] and round(tg["opt"], 3),
+                         "graph_speedup_pct": round(100 * (tg["ref"] / tg["opt"] - 1), 1) if both else None})
             log(f"{name:<14}{dname:<9}{len(opt.optimized_stacks):>7}{n_opt:>6}{t['ref']:>16.3f}{t['opt']:>14.3f}"
-                f"{100 * (t['ref'] / t['opt'] - 1):>12.1f}")
+                f"{100 * (t['ref'] / t['opt'] - 1):>12.1f}" +
+                (f"{tg['ref']:>12.3f}{tg['opt']:>12.3f}{100 * (tg['ref'] / tg['opt'] - 1):>12.1f}" if both else "   graph replay differs"))
             for st in opt.optimized_stacks:
                 st.close()
             del ref, opt, xs
