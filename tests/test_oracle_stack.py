@@ -253,3 +253,33 @@ def test_runner_argument_errors():
         bf.run_stack([wl.relu()], x, [x])
     with pytest.raises(ValueError):
         bf.run_stack([{"kind": "conv"}], x)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_max_pool_commutes_with_non_decreasing_lists_that_hold_a_relu(dtype):
+    """The identity behind running a max pool before the element-wise list in front of it
+    (when no argmax is wanted): for operations that never decrease -- BatchNorm with scales
+    >= 0, ReLU, leaky ReLU with slope >= 0, clamp, the roundings to the storage type --
+    max_i f(x_i) and f(max_i x_i) are the same number, and once a ReLU has made every zero +0
+    the same bits.  Checked on the oracle alone: both layer orders, bit for bit, with zeros of
+    both signs and a zero BatchNorm shift in the input; and the identity must fail to hold
+    where it is not claimed (negative scales)."""
+    c, shape = 6, (2, 6, 11, 13)
+    x = wl.activation(shape, 77, dtype)
+    x[:, :, ::3, ::2] = 0.0
+    x[:, :, 1::3, 1::2] = -0.0
+    bn = wl.bn_params(c, 78)
+    zero = wl.bn_params(c, 79)
+    zero["beta"] = np.zeros(c, np.float32)
+    zero["mean"] = np.zeros(c, np.float32)
+    for pool in (wl.maxpool(3, 2, 1), wl.maxpool(2, 2), wl.maxpool(3, 1, 1), wl.maxpool((2, 3), (1, 2), (1, 1))):
+        for lst in ([bn, wl.relu()], [zero, wl.relu()], [wl.relu(), bn, wl.leaky_relu(0.1), wl.clamp(-0.5, 2.0)],
+                    [wl.relu()], [wl.clamp(-1.0, 1.0), wl.relu(), zero]):
+            a, _, _ = bf.run_stack(lst + [pool], x, [], dtype)
+            b, _, _ = bf.run_stack([pool] + lst, x, [], dtype)
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    neg = wl.bn_params(c, 80)
+    neg["gamma"] = -neg["gamma"]
+    a, _, _ = bf.run_stack([neg, wl.relu(), wl.maxpool(3, 2, 1)], x, [], dtype)
+    b, _, _ = bf.run_stack([wl.maxpool(3, 2, 1), neg, wl.relu()], x, [], dtype)
+    assert not np.array_equal(a, b)
