@@ -456,27 +456,28 @@ class Stack:
                                  batch_stride(out), idx, wsp, wsn, st)
         return out, indices
 
-    def run_unchecked(self, x, residuals, out):
-        """`bs_stack_run` on dense tensors of the plan's layout with as little Python in the way
-        as possible (no index outputs): for callers that have validated shapes, dtypes and
-        layouts themselves -- the front-end does, once per call.  The library still checks
-        alignment, aliasing and the workspace."""
+    def run_unchecked(self, x, residuals, out, in_batch_stride=0):
+        """`bs_stack_run_strided` with as little Python in the way as possible (no index outputs;
+        `out` and the residuals dense tensors of the plan's layout; `x` dense, or a channel slice
+        with `in_batch_stride` elements between its images): for callers that have validated
+        shapes, dtypes and layouts themselves -- the front-end does, once per call.  The library
+        still checks alignment, aliasing and the workspace."""
         import torch
         fast = self._fast
         if fast is None:
             lib = load()
             n = self._workspace_bytes
             ws = self.workspace(x.device)
-            fast = self._fast = (lib.bs_stack_run, C.c_void_p(self.handle),
+            fast = self._fast = (lib.bs_stack_run_strided, C.c_void_p(self.handle),
                                  (C.c_void_p * max(1, self.n_res))(), ws.data_ptr() if ws is not None else None, n,
                                  getattr(torch._C, "_cuda_getCurrentRawStream", None), x.device.index)
         fn, h, res, wsp, wsn, raw_stream, dev = fast
         for i, r in enumerate(residuals):
             res[i] = r.data_ptr()
         st = raw_stream(dev) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
-        rc = fn(h, x.data_ptr(), res, out.data_ptr(), None, wsp, wsn, st)
+        rc = fn(h, x.data_ptr(), in_batch_stride, res, out.data_ptr(), 0, None, wsp, wsn, st)
         if rc != 0:
-            _check(rc, "bs_stack_run")
+            _check(rc, "bs_stack_run_strided")
         return out
 
     def _run_nhwc(self, x, residuals, out, indices, stream):

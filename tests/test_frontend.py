@@ -342,6 +342,69 @@ def test_zoo_chain_descriptions_reproduce_the_torch_model(name):
         assert np.abs(got.reshape(want.shape) - want).max() <= 1e-5 * max(1.0, np.abs(want).max()), ch.names
 
 
+def test_prefix_concat_shares_one_buffer_and_falls_back_when_unsure():
+    pc = fe.PrefixConcat(3)
+    a, b, c = torch.randn(2, 3, 4, 4), torch.randn(2, 2, 4, 4), torch.randn(2, 5, 4, 4)
+    want = [a, torch.cat([a, b], 1), torch.cat([a, b, c], 1)]
+    for it in range(3):
+        got = [pc(0, a), pc(1, a, b), pc(2, a, b, c)]
+        assert all(torch.equal(g, w) for g, w in zip(got, want))
+        if it == 0:
+            assert pc.views_returned == 0 and pc.known[5] == 10  # the first pass learns the sizes
+        else:
+            assert pc.views_returned == 3 * it
+            assert got[0].data_ptr() == got[1].data_ptr() == got[2].data_ptr()  # views of one buffer
+            assert not got[1].is_contiguous() and got[2].is_contiguous()
+    n = pc.views_returned
+    # a part that is not the tensor copied earlier in this pass: the ordinary concatenation
+    pc(0, a)
+    other = a.clone()
+    assert torch.equal(pc(1, other, b), want[1]) and pc.views_returned == n + 1
+    assert torch.equal(pc(2, other, b, c), want[2]) and pc.views_returned == n + 1
+    # another batch size: learnt again, then shared again
+    a2, b2, c2 = a[:1].contiguous(), b[:1].contiguous(), c[:1].contiguous()
+    for it in range(2):
+        before = pc.views_returned
+        got = [pc(0, a2), pc(1, a2, b2), pc(2, a2, b2, c2)]
+        assert torch.equal(got[2], torch.cat([a2, b2, c2], 1))
+        assert pc.views_returned == before + (3 if it else 0)
+    # gradients are being recorded: the ordinary concatenation
+    ag = a2.clone().requires_grad_()
+    before = pc.views_returned
+    out = pc(0, ag)
+    assert out.requires_grad and pc.views_returned == before
+
+
+def test_concat_families_are_rewritten_only_when_stacks_read_them():
+    torch.manual_seed(0)
+    g = fe.optimize_graph(zoo.densenet(121, 0.25, 10).eval())
+    assert [c.positions for c in g.concat_buffers] == [7, 13, 25, 17] and {c.when for c in g.concat_buffers} == {"capture"}
+    x = torch.randn(1, 3, 64, 64)
+    with torch.no_grad():  # not capturing: the ordinary concatenation, sizes learnt for later
+        for c in g.concat_buffers:
+            parts = [torch.randn(1, 2, 4, 4) for _ in range(c.positions)]
+            for k in range(c.positions):
+                assert torch.equal(c(k, *parts[:k + 1]), torch.cat(parts[:k + 1], 1))
+            assert c.views_returned == 0 and c.known[5] == 2 * c.positions
+    assert "torch.cat" not in str(g.graph)
+    g = fe.optimize_graph(zoo.densenet(121, 0.25, 10).eval(), share_concat_buffers=False)
+    assert g.concat_buffers == [] and str(g.graph).count("torch.cat") == 62
+
+    class CatIntoConv(nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.conv = nn.Conv2d(4, 4, 1)
+            self.bn = nn.BatchNorm2d(6)
+
+        def forward(self, x):
+            a = torch.cat([x], 1)
+            b = torch.cat([x, self.conv(a)], 1)      # read by a convolution as well: left alone
+            return torch.relu(self.bn(torch.cat([x, b[:, :2]], 1))), self.conv(b[:, :4])
+
+    g = fe.optimize_graph(CatIntoConv().eval())
+    assert g.concat_buffers == [] and len(g.optimized_stacks) == 1
+
+
 class Hazards(nn.Module):
     def __init__(self):
         super().__init__()
@@ -434,10 +497,15 @@ def test_evaluated_architectures_rewritten_match_the_original(name, channels_las
     if channels_last:
         ref = ref.to(memory_format=torch.channels_last)
         x = x.contiguous(memory_format=torch.channels_last)
-    opt = fe.optimize_graph(ref)
+    opt = fe.optimize_graph(ref, share_concat_buffers="always")
     with torch.no_grad():
         want, got = ref(x), opt(x)
+        again = opt(x)  # from the second pass on, dense blocks share one concatenation buffer
     assert (got - want).abs().max().item() <= 2e-4 * max(1.0, want.abs().max().item())
+    assert (again - want).abs().max().item() <= 2e-4 * max(1.0, want.abs().max().item())
+    if name.startswith("densenet"):  # channels_last parts are concatenated the ordinary way
+        shared = [c.views_returned for c in opt.concat_buffers]
+        assert len(shared) == 4 and shared == ([0] * 4 if channels_last else [c.positions for c in opt.concat_buffers])
     used = set()
     for s in opt.optimized_stacks:
         for st in s._plans.values():
@@ -447,13 +515,14 @@ def test_evaluated_architectures_rewritten_match_the_original(name, channels_las
 
 
 @pytest.mark.gpu
-def test_rewritten_model_can_be_captured_in_a_hip_graph():
+@pytest.mark.parametrize("name", ["resnet18", "densenet121"])
+def test_rewritten_model_can_be_captured_in_a_hip_graph(name):
     """A rewritten model captured with torch.cuda.CUDAGraph: the stack calls allocate through
     torch only and launch on the capturing stream.  Replayed several times with eager work of
     the same model in between; every replay must reproduce the eager result (to a tolerance:
     the convolutions around the stacks are not bit-reproducible from run to run)."""
     torch.manual_seed(6)
-    ref = zoo.randomize_batchnorm(zoo.resnet(18, 0.25, 10), 7).eval().cuda()
+    ref = zoo.randomize_batchnorm(ZOO[name](), 7).eval().cuda()
     opt = fe.optimize_graph(ref)
     x = torch.randn(4, 3, 64, 64, device="cuda")
     other = torch.randn(4, 3, 64, 64, device="cuda")
@@ -479,6 +548,9 @@ def test_rewritten_model_can_be_captured_in_a_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert (y - ref(other)).abs().max().item() <= 2e-4 * max(1.0, want.abs().max().item())
+    # dense blocks share one concatenation buffer per block while captured, and only then
+    assert all(c.views_returned == c.positions for c in opt.concat_buffers)
+    assert len(opt.concat_buffers) == (4 if name == "densenet121" else 0)
     del graph
     for s in opt.optimized_stacks:
         s.close()
