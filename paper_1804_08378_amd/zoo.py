@@ -13,7 +13,7 @@ import torch
 import torch.nn.functional as F
 from torch import nn
 
-__all__ = ["vgg_bn", "resnet", "densenet", "randomize_batchnorm"]
+__all__ = ["vgg_bn", "vgg", "resnet", "densenet", "alexnet", "squeezenet", "randomize_batchnorm"]
 
 
 def randomize_batchnorm(model: nn.Module, seed: int = 0) -> nn.Module:
@@ -36,13 +36,14 @@ class VGG(nn.Module):
     """Blocks of 3x3 convolutions, each followed by BatchNorm and ReLU, a 2x2 max pool after
     every block, three fully connected layers."""
 
-    def __init__(self, blocks, width, classes, hidden):
+    def __init__(self, blocks, width, classes, hidden, batch_norm=True):
         super().__init__()
         layers, cin = [], 3
         for n_conv, c in blocks:
             c = max(1, int(c * width))
             for _ in range(n_conv):
-                layers += [nn.Conv2d(cin, c, 3, padding=1), nn.BatchNorm2d(c), nn.ReLU(inplace=True)]
+                layers += [nn.Conv2d(cin, c, 3, padding=1)] + ([nn.BatchNorm2d(c)] if batch_norm else []) + \
+                          [nn.ReLU(inplace=True)]
                 cin = c
             layers.append(nn.MaxPool2d(2, 2))
         self.features = nn.Sequential(*layers)
@@ -56,10 +57,89 @@ class VGG(nn.Module):
         return self.classifier(torch.flatten(x, 1))
 
 
-def vgg_bn(depth: int = 16, width: float = 1.0, classes: int = 1000) -> nn.Module:
+def vgg_bn(depth: int = 16, width: float = 1.0, classes: int = 1000, batch_norm: bool = True) -> nn.Module:
     convs = {11: (1, 1, 2, 2, 2), 13: (2, 2, 2, 2, 2), 16: (2, 2, 3, 3, 3), 19: (2, 2, 4, 4, 4)}[depth]
     blocks = list(zip(convs, (64, 128, 256, 512, 512)))
-    return VGG(blocks, width, classes, max(8, int(4096 * width)))
+    return VGG(blocks, width, classes, max(8, int(4096 * width)), batch_norm)
+
+
+def vgg(depth: int = 16, width: float = 1.0, classes: int = 1000) -> nn.Module:
+    """The same networks without BatchNorm."""
+    return vgg_bn(depth, width, classes, batch_norm=False)
+
+
+# --------------------------------------------------------------------------- AlexNet
+class AlexNet(nn.Module):
+    """Five convolutions (11x11/4, 5x5, three 3x3) with ReLU, 3x3/2 max pools after the first,
+    second and fifth, three fully connected layers with Dropout."""
+
+    def __init__(self, width, classes):
+        super().__init__()
+        c = [max(1, int(v * width)) for v in (64, 192, 384, 256, 256)]
+        self.features = nn.Sequential(
+            nn.Conv2d(3, c[0], 11, 4, 2), nn.ReLU(inplace=True), nn.MaxPool2d(3, 2),
+            nn.Conv2d(c[0], c[1], 5, padding=2), nn.ReLU(inplace=True), nn.MaxPool2d(3, 2),
+            nn.Conv2d(c[1], c[2], 3, padding=1), nn.ReLU(inplace=True),
+            nn.Conv2d(c[2], c[3], 3, padding=1), nn.ReLU(inplace=True),
+            nn.Conv2d(c[3], c[4], 3, padding=1), nn.ReLU(inplace=True), nn.MaxPool2d(3, 2))
+        self.avgpool = nn.AdaptiveAvgPool2d(6)
+        hidden = max(8, int(4096 * width))
+        self.classifier = nn.Sequential(nn.Dropout(), nn.Linear(c[4] * 36, hidden), nn.ReLU(inplace=True),
+                                        nn.Dropout(), nn.Linear(hidden, hidden), nn.ReLU(inplace=True),
+                                        nn.Linear(hidden, classes))
+
+    def forward(self, x):
+        x = self.avgpool(self.features(x))
+        return self.classifier(torch.flatten(x, 1))
+
+
+def alexnet(width: float = 1.0, classes: int = 1000) -> nn.Module:
+    return AlexNet(width, classes)
+
+
+# ------------------------------------------------------------------------ SqueezeNet
+class Fire(nn.Module):
+    """1x1 "squeeze" convolution, then a 1x1 and a 3x3 "expand" convolution side by side, each
+    followed by ReLU; the two expand results are concatenated."""
+
+    def __init__(self, cin, squeeze, expand):
+        super().__init__()
+        self.squeeze = nn.Conv2d(cin, squeeze, 1)
+        self.expand1 = nn.Conv2d(squeeze, expand, 1)
+        self.expand3 = nn.Conv2d(squeeze, expand, 3, padding=1)
+
+    def forward(self, x):
+        x = F.relu(self.squeeze(x))
+        return torch.cat([F.relu(self.expand1(x)), F.relu(self.expand3(x))], 1)
+
+
+class SqueezeNet(nn.Module):
+    def __init__(self, version, width, classes):
+        super().__init__()
+        w = lambda v: max(1, int(v * width))
+        fire = lambda cin, s, e: Fire(w(cin), w(s), w(e))
+        pool = lambda: nn.MaxPool2d(3, 2, ceil_mode=True)
+        if version == "1.0":
+            self.features = nn.Sequential(
+                nn.Conv2d(3, w(96), 7, 2), nn.ReLU(inplace=True), pool(),
+                fire(96, 16, 64), fire(128, 16, 64), fire(128, 32, 128), pool(),
+                fire(256, 32, 128), fire(256, 48, 192), fire(384, 48, 192), fire(384, 64, 256), pool(),
+                fire(512, 64, 256))
+        else:
+            self.features = nn.Sequential(
+                nn.Conv2d(3, w(64), 3, 2), nn.ReLU(inplace=True), pool(),
+                fire(64, 16, 64), fire(128, 16, 64), pool(),
+                fire(128, 32, 128), fire(256, 32, 128), pool(),
+                fire(256, 48, 192), fire(384, 48, 192), fire(384, 64, 256), fire(512, 64, 256))
+        self.classifier = nn.Sequential(nn.Dropout(), nn.Conv2d(w(512), classes, 1), nn.ReLU(inplace=True),
+                                        nn.AdaptiveAvgPool2d(1))
+
+    def forward(self, x):
+        return torch.flatten(self.classifier(self.features(x)), 1)
+
+
+def squeezenet(version: str = "1.0", width: float = 1.0, classes: int = 1000) -> nn.Module:
+    return SqueezeNet(version, width, classes)
 
 
 # ---------------------------------------------------------------------------- ResNet
