@@ -215,7 +215,8 @@ def frontend_stacks(names=("vgg_a", "vgg_b", "vgg_c"), batch=32, reps=50):
             "optimizable_layers_speedup": round(tot_ref / tot_opt, 2)}
 
 
-def frontend_network(batch=32, reps=10, names=("vgg16_bn", "resnet18", "resnet50", "densenet121"),
+def frontend_network(batch=32, reps=10,
+                     names=("alexnet", "squeezenet1.1", "vgg16", "vgg16_bn", "resnet18", "resnet50", "densenet121"),
                      dtypes=("float32", "float16"), channels_last=False):
     """Whole networks of the families Sections 5.2-5.4 evaluate (architectures written from their
     published descriptions in `paper_1804_08378_amd/zoo.py`, hand-written forward methods, random
@@ -227,8 +228,11 @@ def frontend_network(batch=32, reps=10, names=("vgg16_bn", "resnet18", "resnet50
     from paper_1804_08378_amd import frontend as fe
     from paper_1804_08378_amd import zoo
 
-    make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "vgg11_bn": lambda: zoo.vgg_bn(11), "resnet18": lambda: zoo.resnet(18),
-            "resnet50": lambda: zoo.resnet(50), "densenet121": lambda: zoo.densenet(121)}
+    make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "vgg11_bn": lambda: zoo.vgg_bn(11), "vgg16": lambda: zoo.vgg(16),
+            "resnet18": lambda: zoo.resnet(18), "resnet34": lambda: zoo.resnet(34), "resnet50": lambda: zoo.resnet(50),
+            "resnet101": lambda: zoo.resnet(101), "densenet121": lambda: zoo.densenet(121),
+            "alexnet": lambda: zoo.alexnet(), "squeezenet1.0": lambda: zoo.squeezenet("1.0"),
+            "squeezenet1.1": lambda: zoo.squeezenet("1.1")}
     rows = []
     log(f"{'network':<14}{'dtype':<9}{'stacks':>7}{'opt.':>6}{'torch eager ms':>16}{'optimized ms':>14}{'speed-up %':>12}"
         f"{'graph torch':>12}{'graph opt.':>12}{'speed-up %':>12}")

@@ -55,6 +55,8 @@ constexpr int K_ROWS2_VEC16 = 8;
 constexpr int K_ROWS2_VEC32 = 4;  // float32 in the two-level kernel (8, two loads per row, measured 5 % slower: registers)
 constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
+constexpr int K_PLANE_WALK_CELLS = 16;  // whole-plane pooling: planes up to this many cells are walked in global
+                                        // memory by one lane each, larger ones are staged through LDS
 
 // n / d for 0 <= n < 2^31 by multiply-high and shift.
 struct FastDiv {
@@ -136,10 +138,11 @@ struct PoolDirectK {
     EwOp pre[K_MAX_EW], post[K_MAX_EW];
     PoolK pool;
     int32_t C, H, W, Ho, Wo;
-    uint32_t total;      // units = planes * Ho * (W / vec)
-    FastDiv div_wv;      // by W / vec
+    uint32_t total;      // units = planes * Ho * (W / vec); planes for the whole-plane kernels
+    FastDiv div_wv;      // by W / vec (whole-plane kernel staged through LDS: by H * W)
     FastDiv div_ho;      // by Ho
     FastDiv div_c;
+    int32_t ppg, pitch;  // whole-plane kernel staged through LDS: planes per work-group, LDS floats per plane (odd)
 };
 
 struct PoolRowsK {

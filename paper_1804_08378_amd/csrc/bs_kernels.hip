@@ -307,6 +307,80 @@ __global__ __launch_bounds__(256) void plane_pool_kernel(const PoolDirectK k)
 }
 
 // =============================================================================
+// plane_pool_lds_kernel: the same operation for planes of more than a few cells.  A lane that
+// walks its plane in global memory waits for one memory round trip per handful of cells; here
+// a work-group takes k.ppg consecutive planes (one contiguous range of a dense tensor), all its
+// lanes fetch that range together -- coalesced, one round trip, at most eight cells per lane --
+// and leave the values, after the element-wise operations in front of the pool, in LDS; then
+// lane p walks plane p in LDS, in the same row-major order.  The LDS pitch of a plane is odd, so
+// the lanes of the second phase hit different banks.
+// =============================================================================
+template <int DT>
+__global__ __launch_bounds__(256) void plane_pool_lds_kernel(const PoolDirectK k)
+{
+    extern __shared__ float staged[];
+    constexpr int U = 8;
+    const uint32_t hw = (uint32_t)(k.H * k.W);
+    const uint32_t p0 = blockIdx.x * (uint32_t)k.ppg;
+    const uint32_t np = min((uint32_t)k.ppg, k.total - p0);  // planes of this group (the grid covers k.total exactly)
+    const uint32_t n = np * hw;                              // cells of this group
+    for (uint32_t e0 = threadIdx.x; e0 < n; e0 += blockDim.x * U) {
+        Raw<DT, 1> raw[U];
+        uint32_t off[U], pl[U];
+        int32_t c[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t e = min(e0 + u * blockDim.x, n - 1);  // lanes past the end repeat the last cell
+            pl[u] = fdiv(e, k.div_wv);                           // plane within the group
+            const uint32_t plane = p0 + pl[u];
+            const uint32_t img = fdiv(plane, k.div_c);
+            c[u] = (int32_t)(plane - img * (uint32_t)k.C);
+            off[u] = p0 * hw + e;
+            raw[u] = load_raw<DT, 1>(image_base<DT>(k.in, img, k.in_extra), off[u]);
+        }
+        float x[U][1];
+#pragma unroll
+        for (int u = 0; u < U; ++u) unpack<DT, 1>(raw[u], x[u]);
+        apply_ew<DT, 1, U>(x, c, off, k.pre, k.n_pre, k.params, k.C, k.res);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t e = e0 + u * blockDim.x;
+            if (e < n) staged[pl[u] * (uint32_t)k.pitch + (e - pl[u] * hw)] = x[u][0];
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x >= np) return;
+    const uint32_t plane = p0 + threadIdx.x;
+    const uint32_t img = fdiv(plane, k.div_c);
+    const int32_t c1[1] = {(int32_t)(plane - img * (uint32_t)k.C)};
+    const float *cells = staged + threadIdx.x * (uint32_t)k.pitch;
+    const bool is_max = k.pool.kind == OP_MAXPOOL;
+    float acc = is_max ? -INFINITY : 0.0f;
+    int32_t bi = 0;  // first cell of the plane
+    for (uint32_t i0 = 0; i0 < hw; i0 += U) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = cells[min(i0 + u, hw - 1)];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i0 + u < hw) {
+                if (is_max) {
+                    const bool g = v[u] > acc;
+                    acc = g ? v[u] : acc;
+                    bi = g ? (int32_t)(i0 + u) : bi;
+                } else {
+                    acc = acc + v[u];
+                }
+            }
+    }
+    float y[1][1] = {{is_max ? acc : round_store<DT>(acc * k.pool.inv_kk)}};
+    const uint32_t oo[1] = {plane};
+    apply_ew<DT, 1, 1>(y, c1, oo, k.post, k.n_post, k.params, k.C, k.res);
+    store_elems<DT, 1>(image_base<DT>(k.out, img, k.out_extra), plane, y[0]);
+    if (k.idx && is_max) k.idx[plane] = bi;
+}
+
+// =============================================================================
 // Host side: device queries, parameter upload, launchers.
 // =============================================================================
 static bs_status hip_fail(hipError_t e)
@@ -454,6 +528,18 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in_extra = in_extra; k.out_extra = out_extra;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];
+        if (k.ppg > 0) {
+            // staged through LDS: the argument block must describe what the kernel assumes
+            const int64_t hw = (int64_t)k.H * k.W;
+            if (k.pitch < hw || k.ppg > q.threads || (int64_t)k.div_wv.d != hw || q.lds_bytes < (uint64_t)k.ppg * k.pitch * 4 ||
+                q.grid != ((int64_t)k.total + k.ppg - 1) / k.ppg)
+                return BS_ERR_UNSUPPORTED;
+            const size_t lds = (size_t)q.lds_bytes;
+            if (dtype == BS_BF16) plane_pool_lds_kernel<DT_BF16><<<grid, block, lds, st>>>(k);
+            else if (dtype == BS_F16) plane_pool_lds_kernel<DT_F16><<<grid, block, lds, st>>>(k);
+            else plane_pool_lds_kernel<DT_F32><<<grid, block, lds, st>>>(k);
+            break;
+        }
         if (dtype == BS_BF16) plane_pool_kernel<DT_BF16><<<grid, block, 0, st>>>(k);
         else if (dtype == BS_F16) plane_pool_kernel<DT_F16><<<grid, block, 0, st>>>(k);
         else plane_pool_kernel<DT_F32><<<grid, block, 0, st>>>(k);

@@ -539,12 +539,25 @@ static void plan_direct(const bs_stack *s, Sequence &q, bool whole_plane = false
         k.total = (uint32_t)planes;
         k.div_c = make_fastdiv((uint32_t)k.C);
         q.threads = std::min(q.threads, 256);
-        q.grid = (planes + q.threads - 1) / q.threads;
-        q.lds_bytes = 0;
         q.redundancy = 1.0;
         q.tile_rows = q.tile_cols = 1;
-        q.planes_per_group = q.threads;
         q.n_levels = 1;
+        const int64_t hw = (int64_t)k.H * k.W;
+        if (hw > K_PLANE_WALK_CELLS) {
+            // staged through LDS: so many planes per work-group that a lane fetches at most eight
+            // cells (one memory round trip), at most one plane per lane of a wave
+            q.threads = 256;
+            k.ppg = (int32_t)std::max<int64_t>(1, std::min<int64_t>(64, (int64_t)q.threads * 8 / hw));
+            k.pitch = (int32_t)(hw | 1);
+            k.div_wv = make_fastdiv((uint32_t)hw);
+            q.grid = (planes + k.ppg - 1) / k.ppg;
+            q.lds_bytes = (uint64_t)k.ppg * k.pitch * 4;
+            q.planes_per_group = k.ppg;
+            return;
+        }
+        q.grid = (planes + q.threads - 1) / q.threads;
+        q.lds_bytes = 0;
+        q.planes_per_group = q.threads;
         return;
     }
     const int32_t wv = k.W / vec;

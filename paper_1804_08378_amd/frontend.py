@@ -230,17 +230,26 @@ class BrainSlugStack(nn.Module):
         self._plans.clear()
 
 
-def optimize(model: nn.Module, min_layers: int = 1, **plan_opts) -> nn.Module:
+def _lone_activation(layers: List[dict]) -> bool:
+    """Is the run a single activation layer (plus identities)?  Nothing is fused then, and the
+    framework's own in-place activation moves the same bytes with a cheaper call (measured:
+    SqueezeNet, whose stacks are almost all lone ReLUs, ran 3..12 % slower with them replaced)."""
+    real = [l for l in layers if l]
+    return len(real) == 1 and real[0]["kind"] in ("relu", "leaky_relu", "clamp")
+
+
+def optimize(model: nn.Module, min_layers: int = 1, lone_activations: bool = False, **plan_opts) -> nn.Module:
     """Rewrite `model` in place (and return it): every run of at least `min_layers` consecutive
-    optimizable layers inside a Sequential becomes one BrainSlugStack.  `plan_opts` are passed to
-    `bs_stack_plan` (e.g. max_steps_per_sequence)."""
+    optimizable layers inside a Sequential becomes one BrainSlugStack.  A run that is a single
+    activation layer stays in PyTorch unless `lone_activations` is set.  `plan_opts` are passed
+    to `bs_stack_plan` (e.g. max_steps_per_sequence)."""
     model.optimized_stacks = []
     for parent in [m for m in model.modules() if isinstance(m, nn.Sequential)]:
         names = list(parent._modules.keys())
         mods = [parent._modules[n] for n in names]
         for start, stop in find_runs(parent):
             real = [m for m in mods[start:stop] if layer_desc(m)]
-            if len(real) < min_layers:
+            if len(real) < min_layers or (not lone_activations and _lone_activation([layer_desc(m) for m in real])):
                 continue
             stack = BrainSlugStack(mods[start:stop], **plan_opts)
             stack.train(parent.training)
@@ -541,12 +550,13 @@ def _concat_families(gm, stack_names):
 
 
 def optimize_graph(model: nn.Module, min_layers: int = 1, concrete_args=None, share_concat_buffers="capture",
-                   **plan_opts):
+                   lone_activations: bool = False, **plan_opts):
     """Trace `model` with `torch.fx` and return a `GraphModule` in which every chain of at least
     `min_layers` optimizable operations (see `find_chains`) is one BrainSlugStack call.  The model
     itself is not modified; parameters and sub-modules that stay are shared with it.  Models whose
     `forward` depends on tensor values cannot be traced (a `torch.fx` restriction): use `optimize`
-    on those.  `share_concat_buffers` ("capture", "always" or False): the growing channel
+    on those.  A chain that is a single activation stays in PyTorch unless `lone_activations` is
+    set.  `share_concat_buffers` ("capture", "always" or False): the growing channel
     concatenations of densely connected blocks, when only stacks read them, become views of one
     buffer per block (`PrefixConcat`) -- by default only while a HIP graph is being captured.
     `plan_opts` are passed to `bs_stack_plan`."""
@@ -556,7 +566,7 @@ def optimize_graph(model: nn.Module, min_layers: int = 1, concrete_args=None, sh
     stacks = []
     now: Dict[object, object] = {}  # last node of a replaced chain -> the call that stands for it
     for i, ch in enumerate(find_chains(gm)):
-        if ch.real_layers() < min_layers:
+        if ch.real_layers() < min_layers or (not lone_activations and _lone_activation(ch.layers)):
             continue
         stack = BrainSlugStack.from_layers(ch.layers, ch.names, **plan_opts)
         stack.train(model.training)

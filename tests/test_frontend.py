@@ -61,7 +61,7 @@ def test_aggregation_detection_finds_maximal_runs():
 
 
 def test_optimize_replaces_first_layer_and_blanks_the_rest():
-    m = fe.optimize(vgg_like())
+    m = fe.optimize(vgg_like(), lone_activations=True)
     kinds = [type(c).__name__ for c in m]
     assert kinds == ["Conv2d", "BrainSlugStack", "Identity", "Identity", "Conv2d", "BrainSlugStack", "Identity", "Identity",
                      "Identity", "Identity", "Conv2d", "BrainSlugStack", "Flatten", "LazyLinear"]
@@ -77,6 +77,9 @@ def test_optimize_replaces_first_layer_and_blanks_the_rest():
     assert again.optimized_stacks == []
     m2 = fe.optimize(vgg_like(), min_layers=2)
     assert [type(c).__name__ for c in m2][11] == "ReLU" and len(m2.optimized_stacks) == 2
+    # by default a lone activation stays in PyTorch: nothing to fuse
+    m3 = fe.optimize(vgg_like())
+    assert [type(c).__name__ for c in m3][11] == "ReLU" and len(m3.optimized_stacks) == 2
 
 
 def test_only_sequential_containers_are_rewritten():
@@ -319,7 +322,7 @@ def test_stack_counts_of_the_evaluated_architectures():
             "resnet101": lambda: zoo.resnet(101, 0.125, 10), "densenet121": lambda: zoo.densenet(121, 0.25, 10)}
     got = {}
     for name, make in nets.items():
-        g = fe.optimize_graph(make().eval())
+        g = fe.optimize_graph(make().eval(), lone_activations=True)  # the table counts them
         layers = sum(len(s.replaced) - s.n_residuals for s in g.optimized_stacks)
         got[name] = (layers, len(g.optimized_stacks))
     assert got == {"alexnet": (12, 7), "squeezenet1.0": (30, 28), "squeezenet1.1": (30, 28), "vgg16": (23, 15),
@@ -458,8 +461,9 @@ def test_chain_whose_input_is_overwritten_midway_stays_in_pytorch():
 
 
 def test_what_the_graph_front_end_leaves_alone():
-    g = fe.optimize_graph(Hazards().eval())
+    g = fe.optimize_graph(Hazards().eval(), lone_activations=True)
     assert [s.replaced for s in g.optimized_stacks] == [["BatchNorm2d", "add"], ["relu"]]
+    assert [s.replaced for s in fe.optimize_graph(Hazards().eval()).optimized_stacks] == [["BatchNorm2d", "add"]]
     text = str(g.graph)
     assert "relu_" in text and "max_pool2d" in text and text.count("operator.add") + text.count("_operator.add") >= 2
     x = torch.randn(1, 3, 4, 4)
@@ -513,7 +517,7 @@ def test_evaluated_architectures_rewritten_match_the_original(name, channels_las
     if channels_last:
         ref = ref.to(memory_format=torch.channels_last)
         x = x.contiguous(memory_format=torch.channels_last)
-    opt = fe.optimize_graph(ref, share_concat_buffers="always")
+    opt = fe.optimize_graph(ref, share_concat_buffers="always", lone_activations=True)
     with torch.no_grad():
         want, got = ref(x), opt(x)
         again = opt(x)  # from the second pass on, dense blocks share one concatenation buffer
@@ -598,7 +602,7 @@ def test_rewritten_model_matches_the_original_and_the_oracle(dtype):
         ref(x)
     ref = ref.to(dtype)
     x = x.to(dtype)
-    opt = fe.optimize(copy.deepcopy(ref))
+    opt = fe.optimize(copy.deepcopy(ref), lone_activations=True)
     seen = {}
     for i, stack in enumerate(opt.optimized_stacks):
         stack.register_forward_hook(lambda mod, inp, out, i=i: seen.__setitem__(i, (inp[0].detach().clone(), out.detach().clone())))
