@@ -124,7 +124,9 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
 void set_hip_error(int32_t e);
 // bs_nhwc.hip: channels-last kernels (element-wise, and one pooling step per sequence)
 void nhwc_block(const PoolK &p, int32_t vec, int32_t dtype, int32_t &ohb, int32_t &owb);  // output pixels per lane
-bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream);
+int32_t nhwc_plane_group(int64_t hw, int32_t vec, const PoolK &p, int32_t H, int32_t W, int32_t Ho, int32_t Wo);
+bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, uint64_t lds_bytes,
+                      void *stream);
 // bs_rows.hip: *_supported = the signature is in the pre-compiled table; *_buildable = the
 // kernel template can be instantiated for it at run time; *_expr = that instance's name
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);

@@ -195,6 +195,8 @@ struct NhwcK {
     uint32_t total;   // lanes with work: (output) pixels * channel vectors
     FastDiv div_cv;   // by channel vectors per pixel = C / vec
     FastDiv div_wo, div_ho;
+    int32_t cv_group; // whole-plane pooling staged through LDS: channel vectors per work-group (0: not that kernel);
+                      // div_wo then divides by the work-groups per image
 };
 
 #if defined(__HIPCC__)

@@ -587,7 +587,7 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];
-        const bs_status ls = launch_nhwc(k, dtype, q.vec, q.grid, q.threads, stream);
+        const bs_status ls = launch_nhwc(k, dtype, q.vec, q.grid, q.threads, q.lds_bytes, stream);
         if (ls != BS_OK) return ls;
         break;
     }

@@ -19,6 +19,8 @@
 // memory order.  Index outputs hold ih * W + iw like the NCHW ones and are laid out like
 // the output tensor.
 #include "bs_device.h"
+#include <algorithm>
+
 #include "bs_internal.h"
 
 namespace bs {
@@ -252,7 +254,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
         }
 }
 
-// Any window: one output pixel per lane, one cell at a time.
+// Any window: one output pixel per lane, a few cells of a window row at a time.
 template <int DT, int VEC>
 __global__ __launch_bounds__(256) void nhwc_pool_any_kernel(const NhwcK k)
 {
@@ -278,13 +280,25 @@ __global__ __launch_bounds__(256) void nhwc_pool_any_kernel(const NhwcK k)
         acc[e] = is_max ? -INFINITY : 0.0f;
         bi[e] = hlo * k.W + wlo;
     }
+    // row by row, U cells of a row requested at once (cells past the row's end repeat its last
+    // cell and are not taken), taken in row-major order
+    constexpr int U = VEC >= 8 ? 4 : 8;
     for (int32_t ih = hlo; ih < hhi; ++ih)
-        for (int32_t iw = wlo; iw < whi; ++iw) {
-            const uint32_t off1[1] = {(img + (uint32_t)(ih * k.W + iw)) * (uint32_t)k.C + c0};
-            float x[1][VEC];
-            unpack<DT, VEC>(load_raw<DT, VEC>(k.in, off1[0]), x[0]);
-            apply_ew_nhwc<DT, VEC, 1>(x, c0, off1, k.pre, k.n_pre, k.params, k.C, k.res);
-            take_cell<VEC, true>(is_max, x[0], ih * k.W + iw, acc, bi);
+        for (int32_t iw0 = wlo; iw0 < whi; iw0 += U) {
+            uint32_t off[U];
+            Raw<DT, VEC> raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                off[u] = (img + (uint32_t)(ih * k.W + min(iw0 + u, whi - 1))) * (uint32_t)k.C + c0;
+                raw[u] = load_raw<DT, VEC>(k.in, off[u]);
+            }
+            float x[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) unpack<DT, VEC>(raw[u], x[u]);
+            apply_ew_nhwc<DT, VEC, U>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (iw0 + u < whi) take_cell<VEC, true>(is_max, x[u], ih * k.W + iw0 + u, acc, bi);
         }
     float y[1][VEC];
     if (is_max) {
@@ -301,6 +315,92 @@ __global__ __launch_bounds__(256) void nhwc_pool_any_kernel(const NhwcK k)
         store_elems<DT, VEC>(k.out, ooff[0], y[0]);
         if (k.idx && is_max) store_indices<VEC>(k.idx + ooff[0], bi);
     }
+}
+
+// Pooling over the whole plane (the global pooling at the end of a network) for planes of more
+// than a few cells.  A lane of the kernel above would walk the plane one memory round trip
+// after the other.  Here a work-group takes one image and k.cv_group channel vectors: all its
+// lanes fetch the plane's cells of those channels together (at most U per lane, one round
+// trip), take them through the element-wise operations in front of the pool and leave them in
+// LDS; then one lane per channel walks its cells in LDS in row-major order.
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void nhwc_plane_pool_kernel(const NhwcK k)
+{
+    extern __shared__ float staged[];
+    constexpr int U = 8;
+    const uint32_t CV = (uint32_t)k.cv_group, cvn = k.div_cv.d, hw = (uint32_t)(k.H * k.W);
+    const uint32_t n = fdiv(blockIdx.x, k.div_wo);
+    const uint32_t cv0 = (blockIdx.x - n * k.div_wo.d) * CV;  // first channel vector of this group
+    const uint32_t ncv = min(CV, cvn - cv0);
+    const uint32_t cl = threadIdx.x / CV, cv = threadIdx.x - cl * CV;  // cell lane, channel vector
+    const uint32_t cells_per_pass = blockDim.x / CV;
+    const uint32_t img = n * hw;
+    if (cv < ncv && cl < cells_per_pass) {
+        const uint32_t c0 = (cv0 + cv) * VEC;
+        for (uint32_t t0 = cl; t0 < hw; t0 += cells_per_pass * U) {
+            uint32_t off[U];
+            Raw<DT, VEC> raw[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t t = min(t0 + u * cells_per_pass, hw - 1);  // past the end: the last cell again, not stored
+                off[u] = (img + t) * (uint32_t)k.C + c0;
+                raw[u] = load_raw<DT, VEC>(k.in, off[u]);
+            }
+            float x[U][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) unpack<DT, VEC>(raw[u], x[u]);
+            apply_ew_nhwc<DT, VEC, U>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t t = t0 + u * cells_per_pass;
+                if (t < hw) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) staged[(t * CV + cv) * VEC + e] = x[u][e];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x >= ncv * VEC) return;
+    // lane -> one channel; its cells lie CV * VEC floats apart in LDS
+    const bool is_max = k.pool.kind == OP_MAXPOOL;
+    float acc = is_max ? -INFINITY : 0.0f;
+    int32_t bi = 0;
+    const float *cells = staged + threadIdx.x;
+    const uint32_t pitch = CV * VEC;
+    for (uint32_t t0 = 0; t0 < hw; t0 += U) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = cells[min(t0 + u, hw - 1) * pitch];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (t0 + u < hw) {
+                if (is_max) {
+                    const bool g = v[u] > acc;
+                    acc = g ? v[u] : acc;
+                    bi = g ? (int32_t)(t0 + u) : bi;
+                } else {
+                    acc = acc + v[u];
+                }
+            }
+    }
+    const uint32_t c = cv0 * VEC + threadIdx.x;  // the lane's channel
+    float y[1][1] = {{is_max ? acc : round_store<DT>(acc * k.pool.inv_kk)}};
+    const uint32_t ooff[1] = {n * (uint32_t)k.C + c};
+    apply_ew_nhwc<DT, 1, 1>(y, c, ooff, k.post, k.n_post, k.params, k.C, k.res);
+    store_elems<DT, 1>(k.out, ooff[0], y[0]);
+    if (k.idx && is_max) k.idx[ooff[0]] = bi;
+}
+
+// Channel vectors per work-group of nhwc_plane_pool_kernel for a plane of hw cells (0: the plane
+// is small enough for the one-pixel-per-lane kernel): at most 48 KiB of LDS, at most 32 vectors,
+// a divisor of the work-group size.
+int32_t nhwc_plane_group(int64_t hw, int32_t vec, const PoolK &p, int32_t H, int32_t W, int32_t Ho, int32_t Wo)
+{
+    if (hw <= 16 || p.kh != H || p.kw != W || p.ph != 0 || p.pw != 0 || Ho != 1 || Wo != 1) return 0;
+    int32_t cv = 32;
+    while (cv > 1 && hw * cv * vec * 4 > 48 * 1024) cv /= 2;
+    return hw * cv * vec * 4 > 48 * 1024 ? 0 : cv;
 }
 
 // Output block (rows x columns of output pixels per lane) of the compiled windows.  Measured on
@@ -326,11 +426,22 @@ static void launch_block(const NhwcK &k, dim3 grid, dim3 block, hipStream_t st)
 }
 
 template <int DT, int VEC>
-static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 block, hipStream_t st)
+static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 block, uint64_t lds_bytes, hipStream_t st)
 {
     const PoolK &p = k.pool;
     if (p.kind == 0) {
         nhwc_stream_kernel<DT, VEC, 4><<<grid, block, 0, st>>>(k);
+        return BS_OK;
+    }
+    if (k.cv_group > 0) {
+        // the plan must be the one this kernel assumes: group size, work-groups per image, LDS
+        const int64_t hw = (int64_t)k.H * k.W;
+        const int32_t cv = nhwc_plane_group(hw, VEC, p, k.H, k.W, k.Ho, k.Wo);
+        const int64_t groups = ((int64_t)k.div_cv.d + cv - 1) / std::max(cv, 1);
+        if (cv != k.cv_group || (int64_t)k.div_wo.d != groups || block.x != 256 || 256 % cv != 0 ||
+            lds_bytes < (uint64_t)hw * cv * VEC * 4)
+            return BS_ERR_UNSUPPORTED;
+        nhwc_plane_pool_kernel<DT, VEC><<<grid, block, (size_t)lds_bytes, st>>>(k);
         return BS_OK;
     }
     int32_t ohb, owb;
@@ -353,7 +464,8 @@ static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 bl
     return BS_OK;
 }
 
-bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream)
+bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, uint64_t lds_bytes,
+                      void *stream)
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (grid < 1 || grid > 0x7fffffffll) return BS_ERR_UNSUPPORTED;
@@ -361,9 +473,9 @@ bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, 
     // the vector width the plan was made for must be one the kernels exist for and must divide C
     if ((vec != 1 && vec != full) || k.C % vec != 0 || (int64_t)k.div_cv.d * vec != k.C) return BS_ERR_UNSUPPORTED;
     const dim3 g((uint32_t)grid), b((uint32_t)threads);
-    if (dtype == BS_F32) return vec == 4 ? launch_nhwc_t<DT_F32, 4>(k, dtype, g, b, st) : launch_nhwc_t<DT_F32, 1>(k, dtype, g, b, st);
-    if (dtype == BS_BF16) return vec == 8 ? launch_nhwc_t<DT_BF16, 8>(k, dtype, g, b, st) : launch_nhwc_t<DT_BF16, 1>(k, dtype, g, b, st);
-    if (dtype == BS_F16) return vec == 8 ? launch_nhwc_t<DT_F16, 8>(k, dtype, g, b, st) : launch_nhwc_t<DT_F16, 1>(k, dtype, g, b, st);
+    if (dtype == BS_F32) return vec == 4 ? launch_nhwc_t<DT_F32, 4>(k, dtype, g, b, lds_bytes, st) : launch_nhwc_t<DT_F32, 1>(k, dtype, g, b, lds_bytes, st);
+    if (dtype == BS_BF16) return vec == 8 ? launch_nhwc_t<DT_BF16, 8>(k, dtype, g, b, lds_bytes, st) : launch_nhwc_t<DT_BF16, 1>(k, dtype, g, b, lds_bytes, st);
+    if (dtype == BS_F16) return vec == 8 ? launch_nhwc_t<DT_F16, 8>(k, dtype, g, b, lds_bytes, st) : launch_nhwc_t<DT_F16, 1>(k, dtype, g, b, lds_bytes, st);
     return BS_ERR_UNSUPPORTED;
 }
 

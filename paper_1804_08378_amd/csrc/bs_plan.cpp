@@ -472,6 +472,29 @@ static bs_status plan_nhwc(const bs_stack *s, Sequence &q)
         k.W = k.Wo = (int32_t)q.in_shape[3];
     }
     q.variant = seen ? BS_VARIANT_NHWC_POOL : BS_VARIANT_NHWC_STREAM;
+    if (seen) {
+        // pooling over the whole plane, the plane not tiny: staged through LDS, one work-group per
+        // image and group of channel vectors
+        const int64_t hw = (int64_t)k.H * k.W;
+        const int32_t cv = nhwc_plane_group(hw, vec, k.pool, k.H, k.W, k.Ho, k.Wo);
+        if (cv > 0) {
+            const int32_t groups = (C / vec + cv - 1) / cv;
+            k.cv_group = cv;
+            k.total = (uint32_t)(q.in_shape[0] * groups);
+            k.div_cv = make_fastdiv((uint32_t)(C / vec));
+            k.div_wo = make_fastdiv((uint32_t)groups);
+            k.div_ho = make_fastdiv(1u);
+            q.variant = BS_VARIANT_NHWC_POOL;
+            q.threads = 256;
+            q.grid = (int64_t)k.total;
+            q.lds_bytes = (uint64_t)hw * cv * vec * 4;
+            q.redundancy = 1.0;
+            q.tile_rows = q.tile_cols = 1;
+            q.planes_per_group = cv * vec;
+            q.n_levels = 1;
+            return BS_OK;
+        }
+    }
     // a lane takes one channel vector of a block of ohb x owb output pixels (1 x 1: one pixel)
     int32_t ohb = 1, owb = 1;
     if (seen) nhwc_block(k.pool, vec, s->dtype, ohb, owb);
