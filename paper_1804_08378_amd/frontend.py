@@ -39,8 +39,8 @@ from torch import nn
 from . import brainslug as bs
 from . import workloads as wl
 
-__all__ = ["optimize", "optimize_graph", "find_chains", "BrainSlugStack", "PrefixConcat", "layer_desc",
-           "find_runs", "resolve_layers"]
+__all__ = ["optimize", "optimize_graph", "capture", "CapturedModel", "find_chains", "BrainSlugStack", "PrefixConcat",
+           "layer_desc", "find_runs", "resolve_layers"]
 
 
 def _pair(v) -> Tuple[int, int]:
@@ -599,3 +599,43 @@ def optimize_graph(model: nn.Module, min_layers: int = 1, concrete_args=None, sh
     gm.delete_all_unused_submodules()
     gm.optimized_stacks = stacks
     return gm
+
+
+# ---------------------------------------------------------------------------- HIP graphs
+class CapturedModel:
+    """A model's forward pass for one input shape, recorded once in a HIP graph and replayed:
+    one launch per pass instead of one per kernel, for serving loops that are bound by the host's
+    launch rate.  `__call__` copies its argument into the recorded input buffer, replays the
+    graph and returns the recorded output buffer: the result is overwritten by the next call
+    (clone it to keep it).  Stack calls record nothing but their kernels (no memory is set or
+    allocated outside torch's allocator), so a rewritten model can be captured like any other."""
+
+    def __init__(self, model: nn.Module, example: torch.Tensor, warmup: int = 3):
+        if not example.is_cuda:
+            raise RuntimeError("capture needs an example input on the GPU")
+        self.model = model
+        self.input = example.clone(memory_format=torch.preserve_format)
+        with torch.no_grad():
+            side = torch.cuda.Stream(device=example.device)  # default priority
+            side.wait_stream(torch.cuda.current_stream(example.device))
+            with torch.cuda.stream(side):
+                for _ in range(max(1, warmup)):  # plans, run-time builds, buffer sizes, library warm-up
+                    model(self.input)
+            torch.cuda.current_stream(example.device).wait_stream(side)
+            torch.cuda.synchronize(example.device)
+            self.graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self.graph):
+                self.output = model(self.input)
+
+    def __call__(self, x: torch.Tensor):
+        if x.shape != self.input.shape or x.dtype != self.input.dtype:
+            raise RuntimeError(f"captured for an input of shape {tuple(self.input.shape)} / {self.input.dtype}, "
+                               f"got {tuple(x.shape)} / {x.dtype}")
+        self.input.copy_(x)
+        self.graph.replay()
+        return self.output
+
+
+def capture(model: nn.Module, example: torch.Tensor, warmup: int = 3) -> CapturedModel:
+    """Record `model(example)` (inference, no gradients) in a HIP graph; see `CapturedModel`."""
+    return CapturedModel(model, example, warmup)

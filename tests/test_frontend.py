@@ -577,6 +577,27 @@ def test_rewritten_model_can_be_captured_in_a_hip_graph(name):
 
 
 @pytest.mark.gpu
+def test_capture_helper_replays_new_inputs():
+    torch.manual_seed(8)
+    ref = zoo.randomize_batchnorm(zoo.densenet(121, 0.25, 10), 9).eval().cuda()
+    opt = fe.optimize_graph(ref)
+    xs = [torch.randn(2, 3, 64, 64, device="cuda") for _ in range(3)]
+    runner = fe.capture(opt, xs[0])
+    with torch.no_grad():
+        for x in xs + xs[::-1]:
+            got = runner(x).clone()
+            want = ref(x)  # eager work between the replays
+            torch.cuda.synchronize()
+            assert (got - want).abs().max().item() <= 2e-4 * max(1.0, want.abs().max().item())
+    with pytest.raises(RuntimeError, match="captured for"):
+        runner(torch.randn(1, 3, 64, 64, device="cuda"))
+    assert all(c.views_returned > 0 for c in opt.concat_buffers)
+    del runner
+    for s in opt.optimized_stacks:
+        s.close()
+
+
+@pytest.mark.gpu
 def test_head_like_model_on_the_gpu():
     ref = head_like(c=16).cuda()
     opt = fe.optimize(copy.deepcopy(ref))
