@@ -469,11 +469,11 @@ class Stack:
             n = self._workspace_bytes
             ws = self.workspace(x.device)
             fast = self._fast = (lib.bs_stack_run_strided, C.c_void_p(self.handle),
-                                 (C.c_void_p * max(1, self.n_res))(), ws.data_ptr() if ws is not None else None, n,
+                                 C.c_void_p * max(1, self.n_res), ws.data_ptr() if ws is not None else None, n,
                                  getattr(torch._C, "_cuda_getCurrentRawStream", None), x.device.index)
-        fn, h, res, wsp, wsn, raw_stream, dev = fast
-        for i, r in enumerate(residuals):
-            res[i] = r.data_ptr()
+        fn, h, res_type, wsp, wsn, raw_stream, dev = fast
+        # a fresh pointer array per call: the library reads it while the interpreter lock is released
+        res = res_type(*[r.data_ptr() for r in residuals]) if residuals else None
         st = raw_stream(dev) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
         rc = fn(h, x.data_ptr(), in_batch_stride, res, out.data_ptr(), 0, None, wsp, wsn, st)
         if rc != 0:
