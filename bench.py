@@ -216,11 +216,12 @@ def frontend_stacks(names=("vgg_a", "vgg_b", "vgg_c"), batch=32, reps=50):
 
 
 def frontend_network(batch=32, reps=10,
-                     names=("alexnet", "squeezenet1.1", "vgg16", "vgg16_bn", "resnet18", "resnet50", "densenet121"),
+                     names=("alexnet", "squeezenet1.1", "vgg16", "vgg16_bn", "resnet18", "resnet50", "densenet121",
+                            "inception_v3"),
                      dtypes=("float32", "float16"), channels_last=False):
     """Whole networks of the families Sections 5.2-5.4 evaluate (architectures written from their
     published descriptions in `paper_1804_08378_amd/zoo.py`, hand-written forward methods, random
-    weights, 3 x 224 x 224 inputs), forward pass by PyTorch eager and after
+    weights, 3 x 224 x 224 inputs, 3 x 299 x 299 for Inception), forward pass by PyTorch eager and after
     `frontend.optimize_graph`: convolutions and fully connected layers stay in PyTorch on both
     sides, every chain of BatchNorm / ReLU / Add / pooling operations becomes one stack call.
     `stacks` / `optimizable` are what the paper's detail table calls Stacks / Opt."""
@@ -232,7 +233,7 @@ def frontend_network(batch=32, reps=10,
             "resnet18": lambda: zoo.resnet(18), "resnet34": lambda: zoo.resnet(34), "resnet50": lambda: zoo.resnet(50),
             "resnet101": lambda: zoo.resnet(101), "densenet121": lambda: zoo.densenet(121),
             "alexnet": lambda: zoo.alexnet(), "squeezenet1.0": lambda: zoo.squeezenet("1.0"),
-            "squeezenet1.1": lambda: zoo.squeezenet("1.1")}
+            "squeezenet1.1": lambda: zoo.squeezenet("1.1"), "inception_v3": lambda: zoo.inception_v3()}
     rows = []
     log(f"{'network':<14}{'dtype':<9}{'stacks':>7}{'opt.':>6}{'torch eager ms':>16}{'optimized ms':>14}{'speed-up %':>12}"
         f"{'graph torch':>12}{'graph opt.':>12}{'speed-up %':>12}")
@@ -241,7 +242,8 @@ def frontend_network(batch=32, reps=10,
             dtype = getattr(torch, dname)
             torch.manual_seed(0)
             ref = zoo.randomize_batchnorm(make[name]()).cuda().eval().to(dtype)
-            xs = [torch.randn(batch, 3, 224, 224, device="cuda").to(dtype) for _ in range(2)]
+            size = 299 if name.startswith("inception") else 224
+            xs = [torch.randn(batch, 3, size, size, device="cuda").to(dtype) for _ in range(2)]
             if channels_last:
                 ref = ref.to(memory_format=torch.channels_last)
                 xs = [x.contiguous(memory_format=torch.channels_last) for x in xs]

@@ -13,7 +13,7 @@ import torch
 import torch.nn.functional as F
 from torch import nn
 
-__all__ = ["vgg_bn", "vgg", "resnet", "densenet", "alexnet", "squeezenet", "randomize_batchnorm"]
+__all__ = ["vgg_bn", "vgg", "resnet", "densenet", "alexnet", "squeezenet", "inception_v3", "randomize_batchnorm"]
 
 
 def randomize_batchnorm(model: nn.Module, seed: int = 0) -> nn.Module:
@@ -268,3 +268,116 @@ def densenet(depth: int = 121, width: float = 1.0, classes: int = 1000) -> nn.Mo
     growth, counts, c0 = {121: (32, (6, 12, 24, 16), 64), 169: (32, (6, 12, 32, 32), 64),
                           201: (32, (6, 12, 48, 32), 64), 161: (48, (6, 12, 36, 24), 96)}[depth]
     return DenseNet(max(1, int(growth * width)), counts, max(2, int(c0 * width)), classes)
+
+
+# ---------------------------------------------------------------------- Inception v3
+class ConvBN(nn.Module):
+    """Convolution without bias, BatchNorm (eps 0.001), ReLU: the unit every branch is made of."""
+
+    def __init__(self, cin, cout, k, stride=1, padding=0):
+        super().__init__()
+        self.conv = nn.Conv2d(cin, cout, k, stride, padding, bias=False)
+        self.bn = nn.BatchNorm2d(cout, eps=0.001)
+
+    def forward(self, x):
+        return F.relu(self.bn(self.conv(x)))
+
+
+class InceptionA(nn.Module):  # 35 x 35 grid
+    def __init__(self, cin, pool_features, w):
+        super().__init__()
+        self.b1 = ConvBN(cin, w(64), 1)
+        self.b5 = nn.Sequential(ConvBN(cin, w(48), 1), ConvBN(w(48), w(64), 5, padding=2))
+        self.b3 = nn.Sequential(ConvBN(cin, w(64), 1), ConvBN(w(64), w(96), 3, padding=1), ConvBN(w(96), w(96), 3, padding=1))
+        self.bp = ConvBN(cin, w(pool_features), 1)
+
+    def forward(self, x):
+        return torch.cat([self.b1(x), self.b5(x), self.b3(x), self.bp(F.avg_pool2d(x, 3, 1, 1))], 1)
+
+
+class InceptionB(nn.Module):  # 35 -> 17
+    def __init__(self, cin, w):
+        super().__init__()
+        self.b3 = ConvBN(cin, w(384), 3, 2)
+        self.bd = nn.Sequential(ConvBN(cin, w(64), 1), ConvBN(w(64), w(96), 3, padding=1), ConvBN(w(96), w(96), 3, 2))
+
+    def forward(self, x):
+        return torch.cat([self.b3(x), self.bd(x), F.max_pool2d(x, 3, 2)], 1)
+
+
+class InceptionC(nn.Module):  # 17 x 17 grid, factorised 7 x 7 convolutions
+    def __init__(self, cin, c7, w):
+        super().__init__()
+        c7 = w(c7)
+        self.b1 = ConvBN(cin, w(192), 1)
+        self.b7 = nn.Sequential(ConvBN(cin, c7, 1), ConvBN(c7, c7, (1, 7), padding=(0, 3)),
+                                ConvBN(c7, w(192), (7, 1), padding=(3, 0)))
+        self.bd = nn.Sequential(ConvBN(cin, c7, 1), ConvBN(c7, c7, (7, 1), padding=(3, 0)),
+                                ConvBN(c7, c7, (1, 7), padding=(0, 3)), ConvBN(c7, c7, (7, 1), padding=(3, 0)),
+                                ConvBN(c7, w(192), (1, 7), padding=(0, 3)))
+        self.bp = ConvBN(cin, w(192), 1)
+
+    def forward(self, x):
+        return torch.cat([self.b1(x), self.b7(x), self.bd(x), self.bp(F.avg_pool2d(x, 3, 1, 1))], 1)
+
+
+class InceptionD(nn.Module):  # 17 -> 8
+    def __init__(self, cin, w):
+        super().__init__()
+        self.b3 = nn.Sequential(ConvBN(cin, w(192), 1), ConvBN(w(192), w(320), 3, 2))
+        self.b7 = nn.Sequential(ConvBN(cin, w(192), 1), ConvBN(w(192), w(192), (1, 7), padding=(0, 3)),
+                                ConvBN(w(192), w(192), (7, 1), padding=(3, 0)), ConvBN(w(192), w(192), 3, 2))
+
+    def forward(self, x):
+        return torch.cat([self.b3(x), self.b7(x), F.max_pool2d(x, 3, 2)], 1)
+
+
+class InceptionE(nn.Module):  # 8 x 8 grid, branches that split once more
+    def __init__(self, cin, w):
+        super().__init__()
+        self.b1 = ConvBN(cin, w(320), 1)
+        self.b3 = ConvBN(cin, w(384), 1)
+        self.b3a = ConvBN(w(384), w(384), (1, 3), padding=(0, 1))
+        self.b3b = ConvBN(w(384), w(384), (3, 1), padding=(1, 0))
+        self.bd = nn.Sequential(ConvBN(cin, w(448), 1), ConvBN(w(448), w(384), 3, padding=1))
+        self.bda = ConvBN(w(384), w(384), (1, 3), padding=(0, 1))
+        self.bdb = ConvBN(w(384), w(384), (3, 1), padding=(1, 0))
+        self.bp = ConvBN(cin, w(192), 1)
+
+    def forward(self, x):
+        b3 = self.b3(x)
+        bd = self.bd(x)
+        return torch.cat([self.b1(x), torch.cat([self.b3a(b3), self.b3b(b3)], 1),
+                          torch.cat([self.bda(bd), self.bdb(bd)], 1), self.bp(F.avg_pool2d(x, 3, 1, 1))], 1)
+
+
+class InceptionV3(nn.Module):
+    """299 x 299 input; five convolutions and two 3x3/2 max pools, three A, one B, four C, one D
+    and two E modules, global average pool, Dropout, one fully connected layer (no auxiliary
+    classifier)."""
+
+    def __init__(self, width, classes):
+        super().__init__()
+        w = lambda v: max(1, int(v * width))
+        self.stem1 = nn.Sequential(ConvBN(3, w(32), 3, 2), ConvBN(w(32), w(32), 3), ConvBN(w(32), w(64), 3, padding=1))
+        self.stem2 = nn.Sequential(ConvBN(w(64), w(80), 1), ConvBN(w(80), w(192), 3))
+        a1, a2, a3 = w(64) + w(64) + w(96) + w(32), w(64) + w(64) + w(96) + w(64), w(64) + w(64) + w(96) + w(64)
+        b = w(384) + w(96) + a3
+        d = w(320) + w(192) + 4 * w(192)
+        e = w(320) + 4 * w(384) + w(192)
+        self.mixed = nn.Sequential(
+            InceptionA(w(192), 32, w), InceptionA(a1, 64, w), InceptionA(a2, 64, w), InceptionB(a3, w),
+            InceptionC(b, 128, w), InceptionC(4 * w(192), 160, w), InceptionC(4 * w(192), 160, w),
+            InceptionC(4 * w(192), 192, w), InceptionD(4 * w(192), w), InceptionE(d, w), InceptionE(e, w))
+        self.dropout = nn.Dropout()
+        self.fc = nn.Linear(e, classes)
+
+    def forward(self, x):
+        x = F.max_pool2d(self.stem1(x), 3, 2)
+        x = F.max_pool2d(self.stem2(x), 3, 2)
+        x = self.dropout(F.adaptive_avg_pool2d(self.mixed(x), 1))
+        return self.fc(torch.flatten(x, 1))
+
+
+def inception_v3(width: float = 1.0, classes: int = 1000) -> nn.Module:
+    return InceptionV3(width, classes)

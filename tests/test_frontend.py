@@ -297,15 +297,18 @@ def test_chain_descriptions_reproduce_the_torch_model(name):
 
 # ------------------------------------------------------------------ the evaluated architectures
 ZOO = {"vgg16_bn": lambda: zoo.vgg_bn(16, 0.125, 10), "resnet18": lambda: zoo.resnet(18, 0.125, 10),
-       "resnet50": lambda: zoo.resnet(50, 0.125, 10), "densenet121": lambda: zoo.densenet(121, 0.25, 10)}
+       "resnet50": lambda: zoo.resnet(50, 0.125, 10), "densenet121": lambda: zoo.densenet(121, 0.25, 10),
+       "inception_v3": lambda: zoo.inception_v3(0.125, 10), "squeezenet1.0": lambda: zoo.squeezenet("1.0", 0.25, 10),
+       "alexnet": lambda: zoo.alexnet(0.25, 10)}
+ZOO_INPUT = {"vgg16_bn": 224, "inception_v3": 299, "squeezenet1.0": 224, "alexnet": 224}  # others: 64
 
 
 def test_stack_counts_of_the_evaluated_architectures():
     """Aggregation detection on the architectures of Section 5 (their structure does not depend
     on the width) against the "Opt." and "Stacks" columns of the paper's detail table:
       * optimizable layers (Dropout included, residual additions not: the paper's layer list
-        has none): equal to the table for ResNet-18/34/50/101 (39, 71, 104, 206) and
-        DenseNet-121 (247); one more for the VGGs (22, 25, 35, 41 in the table: the adaptive
+        has none): equal to the table for ResNet-18/34/50/101 (39, 71, 104, 206),
+        DenseNet-121 (247) and Inception v3 (203; 106 stacks here, 103 in the table); one more for the VGGs (22, 25, 35, 41 in the table: the adaptive
         average pool before the classifier is absent from the model definitions of the
         paper's time); AlexNet 12 as in the table (that pool more, its leading Dropout less);
         one fewer for SqueezeNet (31 in the table: its Dropout, a run without a real layer);
@@ -319,7 +322,8 @@ def test_stack_counts_of_the_evaluated_architectures():
             "vgg11_bn": lambda: zoo.vgg_bn(11, 0.125, 10), "vgg16_bn": lambda: zoo.vgg_bn(16, 0.125, 10),
             "vgg19_bn": lambda: zoo.vgg_bn(19, 0.125, 10), "resnet18": lambda: zoo.resnet(18, 0.125, 10),
             "resnet34": lambda: zoo.resnet(34, 0.125, 10), "resnet50": lambda: zoo.resnet(50, 0.125, 10),
-            "resnet101": lambda: zoo.resnet(101, 0.125, 10), "densenet121": lambda: zoo.densenet(121, 0.25, 10)}
+            "resnet101": lambda: zoo.resnet(101, 0.125, 10), "densenet121": lambda: zoo.densenet(121, 0.25, 10),
+            "inception_v3": lambda: zoo.inception_v3(0.125, 10)}
     got = {}
     for name, make in nets.items():
         g = fe.optimize_graph(make().eval(), lone_activations=True)  # the table counts them
@@ -327,7 +331,8 @@ def test_stack_counts_of_the_evaluated_architectures():
         got[name] = (layers, len(g.optimized_stacks))
     assert got == {"alexnet": (12, 7), "squeezenet1.0": (30, 28), "squeezenet1.1": (30, 28), "vgg16": (23, 15),
                    "vgg11_bn": (26, 10), "vgg16_bn": (36, 15), "vgg19_bn": (42, 18), "resnet18": (39, 20),
-                   "resnet34": (71, 36), "resnet50": (104, 53), "resnet101": (206, 104), "densenet121": (247, 124)}
+                   "resnet34": (71, 36), "resnet50": (104, 53), "resnet101": (206, 104), "densenet121": (247, 124),
+                   "inception_v3": (203, 106)}
 
 
 @pytest.mark.parametrize("name", ["vgg16_bn", "resnet50", "densenet121"])
@@ -346,7 +351,7 @@ def test_zoo_chain_descriptions_reproduce_the_torch_model(name):
             return v
 
     with torch.no_grad():
-        size = 224 if name.startswith("vgg") else 64  # VGG's adaptive pool needs a 7 x 7 (or 14 x 14 ...) plane
+        size = ZOO_INPUT.get(name, 64)  # VGG's adaptive pool needs a 7 x 7 (or 14 x 14 ...) plane
         Recorder(gm).run(torch.randn(1, 3, size, size, generator=torch.Generator().manual_seed(2)))
     chains = fe.find_chains(gm)
     for ch in chains[::3]:  # every third chain keeps the test short
@@ -512,7 +517,7 @@ def test_evaluated_architectures_rewritten_match_the_original(name, channels_las
     through the library as well), also with channels_last tensors."""
     torch.manual_seed(4)
     ref = zoo.randomize_batchnorm(ZOO[name](), 5).eval().cuda()
-    size = 224 if name.startswith("vgg") else 64
+    size = ZOO_INPUT.get(name, 64)
     x = torch.randn(2, 3, size, size, device="cuda")
     if channels_last:
         ref = ref.to(memory_format=torch.channels_last)
