@@ -123,8 +123,9 @@ struct StreamK {
     EwOp ew[K_MAX_STREAM_EW];
     uint32_t total;     // vectors (or elements when vec == 1)
     int32_t C;
-    FastDiv div_plane;  // by H*W/vec
+    FastDiv div_plane;  // by H*W/vec (flat: by H*W)
     FastDiv div_c;
+    int32_t flat;       // 1: H*W is no multiple of vec; vectors run over the whole tensor and may straddle two planes
 };
 
 struct PoolDirectK {

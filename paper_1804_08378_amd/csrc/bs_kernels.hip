@@ -124,6 +124,65 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
 }
 
 // =============================================================================
+// stream_flat_kernel: the same for planes whose size is no multiple of the vector width (the
+// 35 x 35, 17 x 17, 147 x 147 grids of Inception-style networks).  The tensor is taken as one
+// run of 128-bit vectors; a vector may begin in one plane and end in the next (never further:
+// a plane has at least VEC cells), so BatchNorm picks each element's parameters from the two
+// channels involved.  With 16-bit storage this doubles the throughput of the scalar kernel.
+// Dense tensors only (a vector may straddle two images as well).
+// =============================================================================
+template <int DT, int VEC, int U>
+__global__ __launch_bounds__(512) void stream_flat_kernel(const StreamK k)
+{
+    const uint32_t nthr = blockDim.x;
+    const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
+    const uint32_t hw = k.div_plane.d;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t i = base + u * nthr;
+        const bool valid = i < k.total;
+        i = valid ? i : 0u;
+        const uint32_t off = i * VEC;
+        const uint32_t plane = fdiv(off, k.div_plane);
+        const uint32_t nfirst = hw - (off - plane * hw);  // elements of the vector that lie in `plane`
+        const uint32_t c0 = plane - fdiv(plane, k.div_c) * (uint32_t)k.C;
+        const uint32_t c1 = c0 + 1 == (uint32_t)k.C ? 0u : c0 + 1;
+        float x[VEC];
+        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.in, off), x);
+#pragma clang loop unroll(disable)
+        for (int32_t j = 0; j < k.n_ew; ++j) {
+            const int32_t kind = k.ew[j].kind, arg = k.ew[j].arg;
+            if (kind == OP_BN) {
+                const float sc0 = k.params[arg + c0], sh0 = k.params[arg + k.C + c0];
+                const float sc1 = k.params[arg + c1], sh1 = k.params[arg + k.C + c1];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const bool first = (uint32_t)e < nfirst;
+                    x[e] = round_store<DT>(__builtin_fmaf(x[e], first ? sc0 : sc1, first ? sh0 : sh1));
+                }
+            } else if (kind == OP_RELU) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e] = __builtin_fmaxf(x[e], 0.0f);
+            } else if (kind == OP_LEAKY) {
+                const float slope = k.params[arg];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e] = round_store<DT>(x[e] > 0.0f ? x[e] : x[e] * slope);
+            } else if (kind == OP_CLAMP) {
+                const float lo = k.params[arg], hi = k.params[arg + 1];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e] = round_store<DT>(__builtin_fminf(__builtin_fmaxf(x[e], lo), hi));
+            } else {  // OP_ADD
+                float r[VEC];
+                unpack<DT, VEC>(load_raw<DT, VEC, true>(k.res[arg], off), r);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[e] = round_store<DT>(x[e] + r[e]);
+            }
+        }
+        if (valid) store_elems<DT, VEC>(k.out, off, x);
+    }
+}
+
+// =============================================================================
 // pool_direct_kernel: [element-wise]* pool(k == s, p == 0) [element-wise]*,
 // windows disjoint, one 128-bit column block (VEC input columns) per unit.
 // unit = (plane, output row oh, column block cv); it reads KH rows x VEC columns and
@@ -498,6 +557,27 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in = in; k.out = out; k.params = s->dev_params;
         k.in_extra = in_extra; k.out_extra = out_extra;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
+        if (k.flat) {
+            // planned for vectors that run over plane boundaries: dense tensors only
+            if (q.vec != (dtype == BS_F32 ? 4 : 8) || (int64_t)k.div_plane.d < q.vec) return BS_ERR_UNSUPPORTED;
+            if (in_extra != 0 || out_extra != 0) {
+                // channel slices: the scalar kernel, whose argument block differs in the element count only
+                k.total *= (uint32_t)q.vec;
+                k.flat = 0;
+                const int64_t per_group = (int64_t)q.threads * K_STREAM_U;
+                const dim3 g1((uint32_t)(((int64_t)k.total + per_group - 1) / per_group));
+                if (dtype == BS_BF16) stream_kernel<DT_BF16, 1, K_STREAM_U><<<g1, block, 0, st>>>(k);
+                else if (dtype == BS_F16) stream_kernel<DT_F16, 1, K_STREAM_U><<<g1, block, 0, st>>>(k);
+                else stream_kernel<DT_F32, 1, K_STREAM_U><<<g1, block, 0, st>>>(k);
+            } else if (dtype == BS_BF16) {
+                stream_flat_kernel<DT_BF16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            } else if (dtype == BS_F16) {
+                stream_flat_kernel<DT_F16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            } else {
+                stream_flat_kernel<DT_F32, 4, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            }
+            break;
+        }
         if (dtype == BS_BF16) {
             if (q.vec == 8) stream_kernel<DT_BF16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
             else stream_kernel<DT_BF16, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);

@@ -390,7 +390,11 @@ static void plan_stream(const bs_stack *s, Sequence &q)
     q.variant = BS_VARIANT_STREAM;
     const int64_t hw = q.in_shape[2] * q.in_shape[3];
     const int64_t total = q.in_shape[0] * q.in_shape[1] * hw;
-    const int32_t vec = (hw % vec_of(s) == 0) ? vec_of(s) : 1;
+    // planes that are no multiple of the vector width: vectors over the whole tensor (they may
+    // straddle two planes) when the tensor is a whole number of vectors and a plane holds at
+    // least one; the scalar kernel otherwise
+    const bool flat = hw % vec_of(s) != 0 && total % vec_of(s) == 0 && hw >= vec_of(s);
+    const int32_t vec = (hw % vec_of(s) == 0 || flat) ? vec_of(s) : 1;
     q.vec = vec;
     StreamK &k = q.stream;
     k = StreamK{};
@@ -398,7 +402,8 @@ static void plan_stream(const bs_stack *s, Sequence &q)
     for (int32_t i = q.first_op; i < q.first_op + q.n_ops; ++i) fill_ew(s, s->ops[i], q, k.ew[k.n_ew++]);
     k.total = (uint32_t)(total / vec);
     k.C = (int32_t)q.in_shape[1];
-    k.div_plane = make_fastdiv((uint32_t)(hw / vec));
+    k.flat = flat ? 1 : 0;
+    k.div_plane = make_fastdiv((uint32_t)(flat ? hw : hw / vec));
     k.div_c = make_fastdiv((uint32_t)k.C);
     const int64_t per_group = (int64_t)q.threads * K_STREAM_U;
     q.grid = (k.total + per_group - 1) / per_group;

@@ -510,6 +510,30 @@ def test_global_pooling_one_lane_per_plane(shape, dtype):
         check(layers, x, res, dtype, f"global/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
 
 
+# ------------------------------------------------------------------ odd planes
+@pytest.mark.parametrize("shape", [(4, 8, 5, 7), (2, 4, 3, 3), (8, 2, 7, 7), (3, 8, 35, 35), (8, 8, 1, 3), (2, 16, 17, 17)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_elementwise_stacks_on_planes_that_are_no_multiple_of_the_vector_width(shape, dtype):
+    """Element-wise sequences whose plane size is odd but whose tensor is a whole number of
+    128-bit vectors run with vectors that straddle plane (and image) boundaries; BatchNorm then
+    takes each element's parameters from the right one of two channels.  Also as channel slices,
+    where the scalar kernel takes over."""
+    c = shape[1]
+    stacks = {
+        "bn_relu": [wl.bn_params(c, 150), wl.relu()],
+        "bn_add_relu": [wl.bn_params(c, 151), wl.add(), wl.relu()],
+        "two_bn": [wl.relu(), wl.bn_params(c, 152), wl.leaky_relu(0.1), wl.bn_params(c, 153), wl.clamp(-1.0, 1.0), wl.add()],
+        "relu": [wl.relu()],
+    }
+    for name, layers in stacks.items():
+        x = wl.activation(shape, 154, dtype)
+        res = [wl.activation(shape, 155 + i, dtype) for i in range(wl.num_residuals(layers))]
+        info = check(layers, x, res, dtype, f"odd/{name}{shape}")
+        assert [q["variant_name"] for q in info["sequences"]] == ["stream"]
+        if shape[1] == 8:
+            _check_sliced(layers, x, res, dtype, f"odd/{name}{shape}")
+
+
 # ------------------------------------------------------------------ channel slices
 def _run_sliced(layers, x, res, dtype, lead, trail, **opts):
     """Run with the input and the output as channel slices [lead, lead + C) of tensors with
