@@ -167,8 +167,10 @@ typedef enum bs_layout {
  *                           index outputs.  BS_LAYOUT_NHWC plans run one step (one pooling
  *                           operation with the element-wise operations around it) per
  *                           sequence and use their own two kernel families; force_variant
- *                           must be automatic, tile options and jit are ignored, and
- *                           bs_stack_run_strided accepts dense tensors only.  Index outputs
+ *                           must be automatic, tile options and jit are ignored.  A channel
+ *                           slice of a channels-last tensor skips the other channels in
+ *                           every pixel: bs_stack_run_strided takes its batch stride, which
+ *                           must be H * W times the larger tensor's channel count.  Index outputs
  *                           hold the same values (ih * W + iw) in channels-last order.
  */
 typedef struct bs_plan_options {
@@ -304,7 +306,10 @@ BS_API bs_status bs_stack_run(const bs_stack *stack, const void *in, const void 
  *   in_batch_stride    elements between the starts of consecutive images of the input:
  *   out_batch_stride   0 = dense (C*H*W of that tensor), else >= C*H*W; the stride times the
  *                      element size must be a multiple of 16 bytes (BS_ERR_ALIGN)
- * Channels, rows and columns of a slice stay dense (a slice along the channel axis).
+ * Channels, rows and columns of a slice stay dense (a slice along the channel axis).  For a
+ * channels-last plan the slice lies inside every pixel of the larger tensor instead: the batch
+ * stride must be H * W * (channels of the larger tensor), that channel count times the element
+ * size a multiple of 16 bytes, and N * stride at most 2^31 - 1 (BS_ERR_SHAPE / BS_ERR_ALIGN).
  * Residual operands, index outputs and the workspace are dense, as in bs_stack_run.
  * `out` must not overlap an input; two slices of one buffer with the same batch stride count
  * as disjoint when their per-image byte ranges are.  In place (out == in, equal strides) is

@@ -365,6 +365,19 @@ def batch_stride(t):
     return None
 
 
+def batch_stride_nhwc(t):
+    """Batch stride (elements) of a 4-D channels-last tensor that holds its channels contiguously
+    in every pixel of a tensor with at least as many channels -- a channels_last tensor or a
+    slice of one along the channel axis -- else None."""
+    n, c, h, w = t.shape
+    sn, sc, sh, sw = t.stride()
+    ct = sw if w > 1 else (sh if h > 1 else (sn if n > 1 else c))  # channels of the larger tensor
+    if ct >= c and (c == 1 or sc == 1) and (w == 1 or sw == ct) and (h == 1 or sh == w * ct) and \
+            (n == 1 or sn == h * w * ct):
+        return int(h * w * ct)
+    return None
+
+
 # ---- convenience wrapper -----------------------------------------------------------------
 class Stack:
     """A planned stack bound to torch tensors (device memory and streams only)."""

@@ -196,6 +196,8 @@ struct NhwcK {
     uint32_t total;   // lanes with work: (output) pixels * channel vectors
     FastDiv div_cv;   // by channel vectors per pixel = C / vec
     FastDiv div_wo, div_ho;
+    uint32_t in_xp, out_xp;  // elements to skip per pixel beyond the sequence's own C channels: the tensor is a
+                             // channel slice of one with C + in_xp (C + out_xp) channels (0 = dense)
     int32_t cv_group; // whole-plane pooling staged through LDS: channel vectors per work-group (0: not that kernel);
                       // div_wo then divides by the work-groups per image
 };

@@ -662,8 +662,13 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
     }
     case BS_VARIANT_NHWC_STREAM:
     case BS_VARIANT_NHWC_POOL: {
-        if (in_extra != 0 || out_extra != 0) return BS_ERR_UNSUPPORTED;
         NhwcK k = q.nhwc;
+        // a channel slice of a channels-last tensor: the batch stride is a whole number of pixels
+        // of the larger tensor (checked by the caller), the slice skips the same count per pixel
+        const uint32_t hw_in = (uint32_t)(q.in_shape[2] * q.in_shape[3]), hw_out = (uint32_t)(q.out_shape[2] * q.out_shape[3]);
+        if (in_extra % hw_in != 0 || out_extra % hw_out != 0) return BS_ERR_UNSUPPORTED;
+        k.in_xp = in_extra / hw_in;
+        k.out_xp = out_extra / hw_out;
         k.in = in; k.out = out; k.params = s->dev_params;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];

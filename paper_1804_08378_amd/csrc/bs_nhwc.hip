@@ -107,11 +107,12 @@ __global__ __launch_bounds__(512) void nhwc_stream_kernel(const NhwcK k)
         const bool valid = i < k.total;
         i = valid ? i : 0u;
         const uint32_t off1[1] = {i * VEC};
-        const uint32_t c0 = (i - fdiv(i, k.div_cv) * cvn) * VEC;
+        const uint32_t pixel = fdiv(i, k.div_cv);
+        const uint32_t c0 = (i - pixel * cvn) * VEC;
         float x[1][VEC];
-        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.in, off1[0]), x[0]);
+        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.in, off1[0] + pixel * k.in_xp), x[0]);
         apply_ew_nhwc<DT, VEC, 1>(x, c0, off1, k.pre, k.n_pre, k.params, k.C, k.res);
-        if (valid) store_elems<DT, VEC>(k.out, off1[0], x[0]);
+        if (valid) store_elems<DT, VEC>(k.out, off1[0] + pixel * k.out_xp, x[0]);
     }
 }
 
@@ -187,8 +188,9 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
                 // a cell outside the plane is padding: requested from the nearest cell inside
                 // (a safe address) and never used
                 const int32_t ih = min(max(hb + r, 0), k.H - 1), iw = min(max(wb + c, 0), k.W - 1);
-                off[r * CC + c] = (img + (uint32_t)(ih * k.W + iw)) * (uint32_t)k.C + c0;
-                raw[r * CC + c] = load_raw<DT, VEC>(k.in, off[r * CC + c]);
+                const uint32_t pixel = img + (uint32_t)(ih * k.W + iw);
+                off[r * CC + c] = pixel * (uint32_t)k.C + c0;
+                raw[r * CC + c] = load_raw<DT, VEC>(k.in, off[r * CC + c] + pixel * k.in_xp);
             }
 #pragma unroll
         for (int cell = 0; cell < NCELL; ++cell) unpack<DT, VEC>(raw[cell], x[cell]);
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
 
     float y[NOUT][VEC];
     int32_t yi[NOUT][VEC];
-    uint32_t ooff[NOUT];
+    uint32_t ooff[NOUT], opix[NOUT];
     bool oin[NOUT];
 #pragma unroll
     for (int a = 0; a < OHB; ++a)
@@ -207,8 +209,8 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
             const int32_t oh = oh0 + a, ow = ow0 + b;
             oin[o] = oh < k.Ho && ow < k.Wo;
             // outputs beyond the plane's edge (ragged blocks) are computed at a safe address and dropped
-            ooff[o] = ((n * (uint32_t)k.Ho + (uint32_t)min(oh, k.Ho - 1)) * (uint32_t)k.Wo + (uint32_t)min(ow, k.Wo - 1)) *
-                          (uint32_t)k.C + c0;
+            opix[o] = (n * (uint32_t)k.Ho + (uint32_t)min(oh, k.Ho - 1)) * (uint32_t)k.Wo + (uint32_t)min(ow, k.Wo - 1);
+            ooff[o] = opix[o] * (uint32_t)k.C + c0;
             const int32_t h0 = hb + a * SH, w0 = wb + b * SW;
             const int32_t hlo = max(h0, 0), hhi = min(h0 + KH, k.H), wlo = max(w0, 0), whi = min(w0 + KW, k.W);
             float acc[VEC];
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
 #pragma unroll
     for (int o = 0; o < NOUT; ++o)
         if (live && oin[o]) {
-            store_elems<DT, VEC>(k.out, ooff[o], y[o]);
+            store_elems<DT, VEC>(k.out, ooff[o] + opix[o] * k.out_xp, y[o]);
             if constexpr (IDX) {
                 if (is_max) store_indices<VEC>(k.idx + ooff[o], yi[o]);
             }
@@ -289,8 +291,9 @@ __global__ __launch_bounds__(256) void nhwc_pool_any_kernel(const NhwcK k)
             Raw<DT, VEC> raw[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                off[u] = (img + (uint32_t)(ih * k.W + min(iw0 + u, whi - 1))) * (uint32_t)k.C + c0;
-                raw[u] = load_raw<DT, VEC>(k.in, off[u]);
+                const uint32_t pixel = img + (uint32_t)(ih * k.W + min(iw0 + u, whi - 1));
+                off[u] = pixel * (uint32_t)k.C + c0;
+                raw[u] = load_raw<DT, VEC>(k.in, off[u] + pixel * k.in_xp);
             }
             float x[U][VEC];
 #pragma unroll
@@ -312,7 +315,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_any_kernel(const NhwcK k)
     const uint32_t ooff[1] = {pix * (uint32_t)k.C + c0};
     apply_ew_nhwc<DT, VEC, 1>(y, c0, ooff, k.post, k.n_post, k.params, k.C, k.res);
     if (live) {
-        store_elems<DT, VEC>(k.out, ooff[0], y[0]);
+        store_elems<DT, VEC>(k.out, ooff[0] + pix * k.out_xp, y[0]);
         if (k.idx && is_max) store_indices<VEC>(k.idx + ooff[0], bi);
     }
 }
@@ -344,7 +347,7 @@ __global__ __launch_bounds__(256) void nhwc_plane_pool_kernel(const NhwcK k)
             for (int u = 0; u < U; ++u) {
                 const uint32_t t = min(t0 + u * cells_per_pass, hw - 1);  // past the end: the last cell again, not stored
                 off[u] = (img + t) * (uint32_t)k.C + c0;
-                raw[u] = load_raw<DT, VEC>(k.in, off[u]);
+                raw[u] = load_raw<DT, VEC>(k.in, off[u] + (img + t) * k.in_xp);
             }
             float x[U][VEC];
 #pragma unroll
@@ -388,7 +391,7 @@ __global__ __launch_bounds__(256) void nhwc_plane_pool_kernel(const NhwcK k)
     float y[1][1] = {{is_max ? acc : round_store<DT>(acc * k.pool.inv_kk)}};
     const uint32_t ooff[1] = {n * (uint32_t)k.C + c};
     apply_ew_nhwc<DT, 1, 1>(y, c, ooff, k.post, k.n_post, k.params, k.C, k.res);
-    store_elems<DT, 1>(k.out, ooff[0], y[0]);
+    store_elems<DT, 1>(k.out, ooff[0] + n * k.out_xp, y[0]);
     if (k.idx && is_max) k.idx[ooff[0]] = bi;
 }
 

@@ -59,12 +59,29 @@ bs_status check_buffers(const bs_stack *stack, const void *in, int64_t &in_strid
     if (in_stride == 0) in_stride = (int64_t)in_image;
     if (out_stride == 0) out_stride = (int64_t)out_image;
     if (in_stride < (int64_t)in_image || out_stride < (int64_t)out_image) return BS_ERR_SHAPE;
-    // a channel slice of a channels-last tensor is not a batch-strided tensor
-    if (stack->opts.layout == BS_LAYOUT_NHWC && (in_stride != (int64_t)in_image || out_stride != (int64_t)out_image))
-        return BS_ERR_UNSUPPORTED;
+    const bool nhwc = stack->opts.layout == BS_LAYOUT_NHWC;
+    if (nhwc) {
+        // a channel slice of a channels-last tensor: every pixel of the larger tensor holds the
+        // slice's C channels and skips the rest, so the batch stride is a whole number of pixels
+        const int64_t hw_in = stack->in_shape[2] * stack->in_shape[3], hw_out = stack->out_shape[2] * stack->out_shape[3];
+        if (in_stride % hw_in != 0 || out_stride % hw_out != 0) return BS_ERR_SHAPE;
+        if ((uint64_t)(in_stride / hw_in) * es % 16 != 0 && in_stride != (int64_t)in_image) return BS_ERR_ALIGN;
+        if ((uint64_t)(out_stride / hw_out) * es % 16 != 0 && out_stride != (int64_t)out_image) return BS_ERR_ALIGN;
+        if ((uint64_t)in_stride * images > 0x7fffffffull || (uint64_t)out_stride * images > 0x7fffffffull) return BS_ERR_SHAPE;
+    }
     if (in_stride > 0x7fffffffll || out_stride > 0x7fffffffll) return BS_ERR_SHAPE;
-    const Span sin{in, images, in_image * es, (uint64_t)in_stride * es};
-    const Span sout{out, images, out_image * es, (uint64_t)out_stride * es};
+    Span sin{in, images, in_image * es, (uint64_t)in_stride * es};
+    Span sout{out, images, out_image * es, (uint64_t)out_stride * es};
+    if (nhwc) {
+        // the bytes of a channels-last slice's image are spread over the larger tensor's image:
+        // from its first pixel to the slice's channels of its last pixel
+        auto spread = [&](const int64_t *sh, int64_t stride) {
+            const uint64_t hw = (uint64_t)(sh[2] * sh[3]);
+            return ((hw - 1) * ((uint64_t)stride / hw) + (uint64_t)sh[1]) * es;
+        };
+        if (!sin.dense()) sin.image_bytes = spread(stack->in_shape, in_stride);
+        if (!sout.dense()) sout.image_bytes = spread(stack->out_shape, out_stride);
+    }
 
     if (!aligned16(in) || !aligned16(out)) return BS_ERR_ALIGN;
     if (sin.stride_bytes % 16 != 0 && !sin.dense()) return BS_ERR_ALIGN;

@@ -202,15 +202,23 @@ class BrainSlugStack(nn.Module):
         with torch.no_grad():
             # a channels_last tensor stays channels_last: the stack is planned for that memory
             # order and its output is channels_last as well (what the convolutions around it use)
-            nhwc = not x.is_contiguous() and x.is_contiguous(memory_format=torch.channels_last)
+            # a channel slice of a concatenation buffer (of either memory format) is read in
+            # place; other layouts are copied
+            stride, nhwc = 0, False
+            if not x.is_contiguous():
+                nhwc = x.is_contiguous(memory_format=torch.channels_last)
+                if not nhwc:
+                    es = x.element_size()
+                    stride = bs.batch_stride(x)
+                    if stride is None or (x.data_ptr() % 16) or (stride * es) % 16:
+                        stride = bs.batch_stride_nhwc(x)
+                        hw = x.shape[2] * x.shape[3]
+                        if stride is None or (x.data_ptr() % 16) or (stride // hw * es) % 16:
+                            x, stride = x.contiguous(), 0
+                        else:
+                            nhwc = True
             st = self._plans.get((x.shape, x.dtype, nhwc)) or self.plan_for(x.shape, x.dtype, nhwc)
             mf = torch.channels_last if nhwc else torch.contiguous_format
-            # a channel slice of a concatenation buffer is read in place; other layouts are copied
-            stride = 0
-            if not nhwc and not x.is_contiguous():
-                stride = bs.batch_stride(x)
-                if stride is None or (x.data_ptr() % 16) or (stride * x.element_size()) % 16:
-                    x, stride = x.contiguous(), 0
             if len(residuals) != self.n_residuals:
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
             res = []
@@ -482,6 +490,7 @@ class PrefixConcat(nn.Module):
         self._buf = None
         self._parts = []             # data pointers of the parts already in the buffer
         self._channels = 0           # channels of the buffer filled so far
+        self._format = torch.contiguous_format
         self.views_returned = 0      # concatenations answered with a view of the buffer
 
     def forward(self, position: int, *parts: torch.Tensor) -> torch.Tensor:
@@ -493,7 +502,9 @@ class PrefixConcat(nn.Module):
                 k = None
             if k is not None and first.dim() == 4 and \
                     (first.shape[0], first.shape[2], first.shape[3], first.dtype, first.device) == k[:5]:
-                self._buf = torch.empty((k[0], k[5], k[1], k[2]), dtype=k[3], device=k[4])
+                # the buffer has the parts' memory format: NCHW, or channels_last
+                self._format = torch.contiguous_format if first.is_contiguous() else torch.channels_last
+                self._buf = torch.empty((k[0], k[5], k[1], k[2]), dtype=k[3], device=k[4], memory_format=self._format)
         buf, old = self._buf, self._parts
         if buf is not None and len(parts) >= len(old):
             # the parts copied earlier in this pass must be the same tensors (by address); the new
@@ -505,7 +516,7 @@ class PrefixConcat(nn.Module):
             plane = buf.shape[2:]
             for p in new:
                 good = good and p.dim() == 4 and p.shape[2:] == plane and p.shape[0] == buf.shape[0] and \
-                    p.dtype == buf.dtype and p.device == buf.device and p.is_contiguous()
+                    p.dtype == buf.dtype and p.device == buf.device and p.is_contiguous(memory_format=self._format)
             if good and c + sum(p.shape[1] for p in new) <= buf.shape[1]:
                 for p in new:
                     buf.narrow(1, c, p.shape[1]).copy_(p)
@@ -517,8 +528,7 @@ class PrefixConcat(nn.Module):
         # the ordinary way; the largest concatenation of a pass teaches the buffer size
         self._buf = None
         out = torch.cat(parts, 1)
-        if position == self.positions - 1 and first.dim() == 4 and not out.requires_grad and \
-                all(p.is_contiguous() for p in parts):
+        if position == self.positions - 1 and first.dim() == 4 and not out.requires_grad:
             self.known = (first.shape[0], first.shape[2], first.shape[3], first.dtype, first.device, out.shape[1])
         return out
 

@@ -750,6 +750,49 @@ def test_channels_last_max_pool_before_monotone_lists(shape, dtype):
         _check_nhwc(layers, x, res, dtype, f"premax/{name}{shape}")
 
 
+@pytest.mark.parametrize("shape", [(2, 8, 13, 11), (3, 16, 9, 16), (2, 8, 7, 7), (2, 24, 6, 8)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_channels_last_channel_slices(shape, dtype):
+    """Input and output as channel slices of larger channels-last tensors (every pixel holds the
+    slice's channels and skips the others): all channels-last kernels, nothing outside the slices
+    touched.  Eight channels on either side keep every pixel's slice on a 16-byte boundary."""
+    n, c, h, w = shape
+    td, cl = TORCH_DTYPE[dtype], torch.channels_last
+    stacks = {"bn_relu": [wl.bn_params(c, 160), wl.relu()], "bn_add_relu": [wl.bn_params(c, 161), wl.add(), wl.relu()],
+              "stem": [wl.bn_params(c, 162), wl.relu(), wl.maxpool(3, 2, 1, True)],
+              "max2": [wl.relu(), wl.maxpool(2, 2, 0, True), wl.bn_params(c, 163)],
+              "avg3s1": [wl.bn_params(c, 164), wl.relu(), wl.avgpool(3, 1, 1)],
+              "any": [wl.relu(), wl.maxpool((2, 3), (1, 2), (1, 1), True)],
+              "head": [wl.bn_params(c, 165), wl.relu(), wl.avgpool((h, w), (h, w), 0)],
+              "two_pools": [wl.bn_params(c, 166), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1, True), wl.relu()]}
+    for name, layers in stacks.items():
+        print(f"[parity] nhwc-slice/{name}{shape} {dtype}", flush=True)
+        x = wl.activation(shape, 167, dtype)
+        res = [wl.activation(sh, 168 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
+        ref, ref_idx, _ = bf.run_stack(layers, x, res, dtype)
+        st = bs.Stack(layers, shape, dtype).plan(layout=bs.BS_LAYOUT_NHWC)
+        big_in = torch.full((n, c + 16, h, w), float("nan"), dtype=td, device="cuda").contiguous(memory_format=cl)
+        big_in[:, 8:8 + c] = _dev(x, dtype)
+        guard = 4321.0
+        big_out = torch.full((n, c + 16) + tuple(st.out_shape[2:]), guard, dtype=td, device="cuda").contiguous(memory_format=cl)
+        xs, outs = big_in[:, 8:8 + c], big_out[:, 8:8 + c]
+        idx = [torch.empty(bs.bs_stack_index_shape(st.handle, i), dtype=torch.int32, device="cuda").contiguous(memory_format=cl)
+               for i in range(st.n_idx)]
+        resd = [_dev(r, dtype).contiguous(memory_format=cl) for r in res]
+        ws = st.workspace("cuda")
+        bs.bs_stack_run_strided(st.handle, xs.data_ptr(), bs.batch_stride_nhwc(xs), [r.data_ptr() for r in resd],
+                                outs.data_ptr(), bs.batch_stride_nhwc(outs), [t.data_ptr() for t in idx] or None,
+                                ws.data_ptr() if ws is not None else 0, ws.numel() if ws is not None else 0,
+                                torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        out = outs.float().cpu().numpy()
+        assert np.array_equal(np.ascontiguousarray(out).view(np.uint32), ref.view(np.uint32)), name
+        for a, b in zip(idx, ref_idx):
+            assert np.array_equal(a.cpu().numpy(), b), name
+        assert bool((big_out[:, :8] == guard).all()) and bool((big_out[:, 8 + c:] == guard).all()), name
+        st.close()
+
+
 def test_channels_last_argument_checks():
     layers = [wl.bn_params(8, 3), wl.relu(), wl.maxpool(2, 2, 0, True)]
     x = wl.activation((2, 8, 6, 8), 120)
@@ -757,9 +800,9 @@ def test_channels_last_argument_checks():
     xd = _dev(x, "f32")
     with pytest.raises(ValueError, match="channels_last"):
         st.run(xd)  # an NCHW tensor given to a channels-last plan
-    with pytest.raises(bs.BrainSlugError) as e:  # no batch strides for channels-last plans
-        bs.bs_stack_run_strided(st.handle, xd.data_ptr(), 8 * 6 * 8 + 64, None, xd.data_ptr() + (1 << 20), 0, None, 0, 0, 0)
-    assert e.value.status == 4
+    with pytest.raises(bs.BrainSlugError) as e:  # a batch stride that is no whole number of pixels
+        bs.bs_stack_run_strided(st.handle, xd.data_ptr(), 8 * 6 * 8 + 64 - 8, None, xd.data_ptr() + (1 << 20), 0, None, 0, 0, 0)
+    assert e.value.status == 2
     st.close()
     with pytest.raises(bs.BrainSlugError) as e:
         bs.Stack(layers, x.shape, "f32").plan(layout=bs.BS_LAYOUT_NHWC, force_variant=bs.BS_VARIANT_LDS_TILE)

@@ -264,8 +264,15 @@ def test_channels_last_plans_take_one_step_per_sequence():
                 bs.bs_stack_plan(h, host_only=1, **bad)
             assert e.value.status == 3
         bs.bs_stack_plan(h, host_only=1, layout=1)
-        # a channels-last plan takes dense tensors only
-        assert bs.bs_stack_check_buffers(h, 4096, 4 * 8 * 8 + 64, None, 1 << 20, 0, None, 0, 0) == 4
+        # a channel slice of a channels-last tensor: the batch stride is H * W times the larger
+        # tensor's channel count, and that count times the element size a multiple of 16 bytes
         assert bs.bs_stack_check_buffers(h, 4096, 0, None, 1 << 20, 0, None, 0, 0) == 0
+        assert bs.bs_stack_check_buffers(h, 4096, 8 * 8 * 8, None, 1 << 20, 0, None, 0, 0) == 0       # 8 channels
+        assert bs.bs_stack_check_buffers(h, 4096, 0, None, 1 << 20, 8 * 8 * 12, None, 0, 0) == 0      # 12 channels
+        assert bs.bs_stack_check_buffers(h, 4096, 8 * 8 * 8 + 4, None, 1 << 20, 0, None, 0, 0) == 2   # no whole pixels
+        assert bs.bs_stack_check_buffers(h, 4096, 8 * 8 * 5, None, 1 << 20, 0, None, 0, 0) == 7       # 20-byte pixels
+        assert bs.bs_stack_check_buffers(h, 4096, 8 * 8 * 3, None, 1 << 20, 0, None, 0, 0) == 2       # below the image
+        # slices of one channels-last buffer interleave pixel by pixel: refused (not provably disjoint)
+        assert bs.bs_stack_check_buffers(h, 4096, 8 * 8 * 8, None, 4096 + 16, 8 * 8 * 8, None, 0, 0) == 12
     finally:
         bs.bs_stack_destroy(h)
