@@ -379,6 +379,8 @@ def main():
     ap.add_argument("--networks", action="store_true",
                     help="also time whole VGG / ResNet / DenseNet forward passes: PyTorch eager against "
                          "frontend.optimize_graph()")
+    ap.add_argument("--batch-scaling", action="store_true",
+                    help="also time three whole networks at batch sizes 1 .. 128 (float32, NCHW)")
     ap.add_argument("--nhwc", action="store_true",
                     help="also time every configuration with channels-last (NHWC) tensors and plans")
     ap.add_argument("--frontend", action="store_true",
@@ -474,6 +476,10 @@ def main():
     if args.networks:
         out["networks"] = frontend_network()
         out["networks_channels_last"] = frontend_network(dtypes=("float16",), channels_last=True)
+    if args.batch_scaling:
+        # Section 5.4: how both sides scale with the batch size, three networks
+        out["batch_scaling"] = {str(b): frontend_network(batch=b, names=("vgg16_bn", "resnet50", "densenet121"),
+                                                         dtypes=("float32",))["rows"] for b in (1, 4, 16, 64, 128)}
 
     if args.all:
         del stacks
