@@ -136,6 +136,20 @@ def test_plan_option_validation():
         bs.bs_stack_destroy(h)
 
 
+def test_size_limit_is_two_to_the_31_elements():
+    """All index arithmetic is 32-bit: a tensor (input, output or intermediate) of 2^31 elements
+    or more is refused at create, one just below is accepted and plans (host only)."""
+    ok = bs.bs_stack_create([wl.relu(), wl.maxpool(2, 2)], (1, 2047, 1024, 1024), "bf16")
+    try:
+        bs.bs_stack_plan(ok, host_only=1)
+        assert bs.bs_stack_plan_info(ok)["n_sequences"] == 1
+        bs.bs_stack_plan(ok, host_only=1, layout=bs.BS_LAYOUT_NHWC)
+    finally:
+        bs.bs_stack_destroy(ok)
+    for shape in ((1, 2048, 1024, 1024), (2, 1024, 1024, 1024), (65536, 1, 256, 128)):
+        assert _status(bs.bs_stack_create, [wl.relu()], shape, "f32") in (2, 4)
+
+
 def test_buffer_checks_against_brute_force_byte_sets():
     """The argument checks of the strided run (host only, fake addresses): an overlap of the
     output with an input is never let through, slices of one buffer that interleave without

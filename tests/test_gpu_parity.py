@@ -510,6 +510,56 @@ def test_global_pooling_one_lane_per_plane(shape, dtype):
         check(layers, x, res, dtype, f"global/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
 
 
+# ------------------------------------------------------------------ maximum sizes
+def _slice_bn(layers, lo, hi):
+    out = []
+    for l in layers:
+        if l["kind"] == "bn":
+            l = dict(l, **{key: l[key][lo:hi] for key in ("gamma", "beta", "mean", "var")})
+        out.append(l)
+    return out
+
+
+@pytest.mark.parametrize("layout", [bs.BS_LAYOUT_NCHW, bs.BS_LAYOUT_NHWC])
+@pytest.mark.parametrize("dtype,stack", [("bf16", "bn_relu"), ("f16", "bn_relu_max2"), ("bf16", "relu_max3s2p1"),
+                                         ("f32", "bn_add_relu_small")])
+def test_tensors_close_to_the_largest_supported_size(layout, dtype, stack):
+    """Tensors of just under 2^31 elements (the library's limit; all index arithmetic is 32-bit).
+    The input is drawn on the device (seeded); the planes of a few channels from both ends and the
+    middle of the tensor are copied back and checked against the oracle run on those planes alone
+    (every plane is independent of the others in all supported layers)."""
+    c = 2040
+    shape = (1, c, 1024, 1024) if stack != "bn_add_relu_small" else (1, 680, 1024, 1024)  # 2.14e9 / 0.71e9 elements
+    c = shape[1]
+    layers = {"bn_relu": [wl.bn_params(c, 170), wl.relu()],
+              "bn_relu_max2": [wl.bn_params(c, 171), wl.relu(), wl.maxpool(2, 2, 0, True)],
+              "relu_max3s2p1": [wl.relu(), wl.maxpool(3, 2, 1, True)],
+              "bn_add_relu_small": [wl.bn_params(c, 172), wl.add(), wl.relu()]}[stack]
+    td = TORCH_DTYPE[dtype]
+    mf = torch.channels_last if layout == bs.BS_LAYOUT_NHWC else torch.contiguous_format
+    gen = torch.Generator(device="cuda").manual_seed(173)
+    x = torch.empty(shape, dtype=td, device="cuda", memory_format=mf).normal_(generator=gen)
+    res = [torch.empty(shape, dtype=td, device="cuda", memory_format=mf).normal_(generator=gen)
+           for _ in range(wl.num_residuals(layers))]
+    print(f"[parity] max-size {stack} {shape} {dtype} layout={layout}", flush=True)
+    st = bs.Stack(layers, shape, dtype).plan(layout=layout)
+    out, idx = st.run(x, res)
+    torch.cuda.synchronize()
+    info = st.info()
+    st.close()
+    print(f"         variants={[q['variant_name'] for q in info['sequences']]}", flush=True)
+    for p0 in (0, 1, c // 2, c - 2, c - 1):
+        xs = x[:, p0:p0 + 1].float().contiguous().cpu().numpy()
+        rs = [r[:, p0:p0 + 1].float().contiguous().cpu().numpy() for r in res]
+        ref, ref_idx, _ = bf.run_stack(_slice_bn(layers, p0, p0 + 1), xs, rs, dtype)
+        got = out[:, p0:p0 + 1].float().contiguous().cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (stack, p0)
+        for a, b in zip(idx, ref_idx):
+            assert np.array_equal(a[:, p0:p0 + 1].contiguous().cpu().numpy(), b), (stack, p0)
+    del x, res, out, idx
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ odd planes
 @pytest.mark.parametrize("shape", [(4, 8, 5, 7), (2, 4, 3, 3), (8, 2, 7, 7), (3, 8, 35, 35), (8, 8, 1, 3), (2, 16, 17, 17)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
