@@ -174,6 +174,22 @@ def test_deep_synthetic_blocks_split_into_sequences():
             assert info["n_sequences"] > 1
 
 
+@pytest.mark.parametrize("blocks", [5, 12])
+def test_deep_synthetic_blocks_at_the_benchmarked_size(blocks):
+    """The stacked-blocks experiment of Section 5.1 at the size `bench.py --deep` times
+    (64 x 64 x 56 x 56, float32), with the plans it times: whole tensor against the oracle."""
+    c = 64
+    layers = sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 100 + i), wl.relu()] for i in range(blocks)), [])
+    x = wl.activation((64, c, 56, 56), 0)
+    ref, _, _ = bf.run_stack(layers, x, [], "f32")
+    for opts in (dict(), dict(max_steps_per_sequence=5), dict(max_steps_per_sequence=1)):
+        print(f"[parity] deep{blocks} full size opts={opts}", flush=True)
+        out, _, info = run_gpu(layers, x, [], "f32", **opts)
+        assert np.array_equal(out.view(np.uint32), ref.view(np.uint32)), opts
+        if opts.get("max_steps_per_sequence") == 1:
+            assert info["n_sequences"] == blocks
+
+
 def test_in_place_elementwise_and_stream_argument():
     layers, x, res = _shrunk("resnet_tail", "f32", batch=1)
     ref, _, _ = bf.run_stack(layers, x, res)
@@ -841,6 +857,14 @@ def test_channels_last_channel_slices(shape, dtype):
             assert np.array_equal(a.cpu().numpy(), b), name
         assert bool((big_out[:, :8] == guard).all()) and bool((big_out[:, 8 + c:] == guard).all()), name
         st.close()
+
+
+@pytest.mark.parametrize("name,dtype", [("vgg_a", "f32"), ("resnet_stem", "bf16"), ("resnet_tail", "f16"),
+                                        ("densenet_trans", "f32"), ("halo_stress", "f16")])
+def test_channels_last_configs_full_size(name, dtype):
+    """Whole tensors at the BASELINE sizes with channels-last plans, as `bench.py --nhwc` times them."""
+    layers, x, res = wl.inputs_for(name, 0, dtype, indices=False)
+    _check_nhwc(layers, x, res, dtype, f"{name}/full")
 
 
 def test_channels_last_argument_checks():
