@@ -27,11 +27,13 @@ def _dev(a, dtype):
 
 def run_gpu(layers, x, res, dtype, **opts):
     st = bs.Stack(layers, x.shape, dtype).plan(**opts)
-    out, idx = st.run(_dev(x, dtype), [_dev(r, dtype) for r in res])
+    # a channels-last plan takes channels_last tensors; the values read back are the logical N, C, H, W ones
+    mf = torch.channels_last if opts.get("layout") == bs.BS_LAYOUT_NHWC else torch.contiguous_format
+    out, idx = st.run(_dev(x, dtype).contiguous(memory_format=mf), [_dev(r, dtype).contiguous(memory_format=mf) for r in res])
     torch.cuda.synchronize()
     info = st.info()
-    o = out.float().cpu().numpy()
-    ii = [t.cpu().numpy() for t in idx]
+    o = np.ascontiguousarray(out.float().cpu().numpy())
+    ii = [np.ascontiguousarray(t.cpu().numpy()) for t in idx]
     st.close()
     return o, ii, info
 
@@ -415,7 +417,8 @@ def test_random_stacks_match_the_oracle(seed):
         x = wl.activation((n, c, h, w), 2000 + 10 * seed + case, dtype)
         res = [wl.activation((n, c) + rs, 3000 + i, dtype) for i, rs in enumerate(res_shapes)]
         opts = [dict(), dict(jit=-1), dict(force_variant=bs.BS_VARIANT_LDS_TILE), dict(breadth_first=1),
-                dict(max_steps_per_sequence=1)][int(rng.integers(0, 5))]
+                dict(layout=bs.BS_LAYOUT_NHWC),
+                dict(max_steps_per_sequence=1)][int(rng.integers(0, 6))]
         label = f"random/{seed}.{case} {[l['kind'] for l in layers]}"
         try:
             check(layers, x, res, dtype, label, **opts)
