@@ -101,6 +101,31 @@ __global__ __launch_bounds__(512) void nhwc_stream_kernel(const NhwcK k)
     const uint32_t nthr = blockDim.x;
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
     const uint32_t cvn = k.div_cv.d;
+    if (nthr % cvn == 0) {
+        // the lane's U vectors lie a multiple of the channel count apart: the same channels, one
+        // set of BatchNorm parameters for all of them
+        const uint32_t c0 = (base - fdiv(base, k.div_cv) * cvn) * VEC;
+        bool valid[U];
+        uint32_t off[U], pixel[U];
+        Raw<DT, VEC> raw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t i = base + u * nthr;
+            valid[u] = i < k.total;
+            i = valid[u] ? i : base % cvn;  // a vector of the same channels at the start of the tensor
+            off[u] = i * VEC;
+            pixel[u] = fdiv(i, k.div_cv);
+            raw[u] = load_raw<DT, VEC, true>(k.in, off[u] + pixel[u] * k.in_xp);
+        }
+        float x[U][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) unpack<DT, VEC>(raw[u], x[u]);
+        apply_ew_nhwc<DT, VEC, U>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (valid[u]) store_elems<DT, VEC>(k.out, off[u] + pixel[u] * k.out_xp, x[u]);
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         uint32_t i = base + u * nthr;
