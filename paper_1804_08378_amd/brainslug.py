@@ -469,10 +469,10 @@ class Stack:
                                  batch_stride(out), idx, wsp, wsn, st)
         return out, indices
 
-    def run_unchecked(self, x, residuals, out, in_batch_stride=0):
+    def run_unchecked(self, x, residuals, out, in_batch_stride=0, out_batch_stride=0):
         """`bs_stack_run_strided` with as little Python in the way as possible (no index outputs;
-        `out` and the residuals dense tensors of the plan's layout; `x` dense, or a channel slice
-        with `in_batch_stride` elements between its images): for callers that have validated
+        the residuals dense tensors of the plan's layout; `x` / `out` dense, or channel slices with
+        `in_batch_stride` / `out_batch_stride` elements between their images): for callers that have validated
         shapes, dtypes and layouts themselves -- the front-end does, once per call.  The library
         still checks alignment, aliasing and the workspace."""
         import torch
@@ -488,7 +488,7 @@ class Stack:
         # a fresh pointer array per call: the library reads it while the interpreter lock is released
         res = res_type(*[r.data_ptr() for r in residuals]) if residuals else None
         st = raw_stream(dev) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
-        rc = fn(h, x.data_ptr(), in_batch_stride, res, out.data_ptr(), 0, None, wsp, wsn, st)
+        rc = fn(h, x.data_ptr(), in_batch_stride, res, out.data_ptr(), out_batch_stride, None, wsp, wsn, st)
         if rc != 0:
             _check(rc, "bs_stack_run_strided")
         return out

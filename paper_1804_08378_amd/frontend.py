@@ -39,7 +39,7 @@ from torch import nn
 from . import brainslug as bs
 from . import workloads as wl
 
-__all__ = ["optimize", "optimize_graph", "capture", "CapturedModel", "find_chains", "BrainSlugStack", "PrefixConcat",
+__all__ = ["optimize", "optimize_graph", "capture", "CapturedModel", "find_chains", "BrainSlugStack", "PrefixConcat", "ConcatSink",
            "layer_desc", "find_runs", "resolve_layers"]
 
 
@@ -182,8 +182,11 @@ class BrainSlugStack(nn.Module):
             self._plans[key] = st
         return st
 
-    def forward(self, x: torch.Tensor, *residuals: torch.Tensor) -> torch.Tensor:
-        """`residuals`: the second operand of every Add layer of the stack, in layer order."""
+    def forward(self, x: torch.Tensor, *residuals: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """`residuals`: the second operand of every Add layer of the stack, in layer order.  `out`:
+        where to write the result -- a tensor of the output's shape, dense in the input's memory
+        format or a channel slice of such a tensor (a concatenation buffer); when it does not fit
+        (shape, type, alignment) it is ignored and a new tensor is returned."""
         if self.training:
             raise RuntimeError("BrainSlugStack implements the inference forward pass only: call model.eval()")
         if not x.is_cuda:
@@ -227,10 +230,31 @@ class BrainSlugStack(nn.Module):
                     raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
                                        f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
                 res.append(r.contiguous(memory_format=mf))
-            # dense tensors of the plan's layout, or a validated channel slice as input
-            out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf)
-            st.run_unchecked(x, res, out, stride)
+            # dense tensors of the plan's layout, or validated channel slices as input / output
+            ostride = 0
+            if out is not None:
+                ostride = self._slice_stride(out, st.out_shape, x, nhwc)
+                if ostride is None:
+                    out = None
+            if out is None:
+                out, ostride = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf), 0
+            st.run_unchecked(x, res, out, stride, ostride)
         return out
+
+    @staticmethod
+    def _slice_stride(t, shape, like, nhwc):
+        """Batch stride to pass for `t` as an output of `shape` (0: dense), or None when `t` cannot be
+        written in place."""
+        if t.shape != shape or t.dtype != like.dtype or t.device != like.device or (t.data_ptr() % 16):
+            return None
+        if t.is_contiguous(memory_format=torch.channels_last if nhwc else torch.contiguous_format):
+            return 0
+        es = t.element_size()
+        if nhwc:
+            stride = bs.batch_stride_nhwc(t)
+            return stride if stride is not None and (stride // (shape[2] * shape[3]) * es) % 16 == 0 else None
+        stride = bs.batch_stride(t)
+        return stride if stride is not None and (stride * es) % 16 == 0 else None
 
     def close(self) -> None:
         for st in self._plans.values():
@@ -533,6 +557,109 @@ class PrefixConcat(nn.Module):
         return out
 
 
+class ConcatSink(nn.Module):
+    """A channel concatenation some of whose parts are produced by stacks: those stacks write
+    their result straight into their channel range of the concatenated tensor (a channel slice
+    as stack output, `bs_stack_run_strided`), the other parts are copied in as `torch.cat` would,
+    and the concatenation itself disappears for the stack-made parts.
+
+    Three small modules share this state and are called in graph order: `begin` before the first
+    part is computed (it allocates the buffer), `slot(i)` before stack part i (it hands out the
+    view to write into) and `finish` where the concatenation stood.  Shapes are learnt in the
+    first forward pass, which concatenates the ordinary way; `when` as for `PrefixConcat`."""
+
+    def __init__(self, n_parts: int, when: str = "capture"):
+        super().__init__()
+        self.n_parts, self.when = n_parts, when
+        self.known = None    # (N, H, W, dtype, device, memory format, channels per part)
+        self._buf, self._offsets = None, None
+        self.in_place = 0    # parts that arrived already in place
+
+    def begin(self, like: torch.Tensor) -> torch.Tensor:
+        self._buf = None
+        k = self.known
+        if k is not None and like.is_cuda and (self.when == "always" or torch.cuda.is_current_stream_capturing()) and \
+                not (torch.is_grad_enabled() and like.requires_grad) and like.dim() == 4 and \
+                (like.shape[0], like.dtype, like.device) == (k[0], k[3], k[4]):
+            self._buf = torch.empty((k[0], sum(k[6]), k[1], k[2]), dtype=k[3], device=k[4], memory_format=k[5])
+        return like
+
+    def slot(self, i: int) -> Optional[torch.Tensor]:
+        if self._buf is None:
+            return None
+        c = self.known[6]
+        return self._buf.narrow(1, sum(c[:i]), c[i])
+
+    def finish(self, *parts: torch.Tensor) -> torch.Tensor:
+        buf, k = self._buf, self.known
+        self._buf = None
+        first = parts[0]
+        if buf is not None and len(parts) == len(k[6]) and \
+                all(p.dim() == 4 and p.shape[1] == c and p.shape[0] == k[0] and p.shape[2:] == buf.shape[2:] and
+                    p.dtype == buf.dtype and p.device == buf.device for p, c in zip(parts, k[6])):
+            off = 0
+            for p, c in zip(parts, k[6]):
+                view = buf.narrow(1, off, c)
+                if p.data_ptr() == view.data_ptr() and p.stride() == view.stride():
+                    self.in_place += 1
+                else:
+                    view.copy_(p)
+                off += c
+            return buf
+        out = torch.cat(parts, 1)
+        if first.dim() == 4 and not out.requires_grad:
+            mf = torch.contiguous_format if out.is_contiguous() else torch.channels_last
+            if out.is_contiguous(memory_format=mf):
+                self.known = (out.shape[0], out.shape[2], out.shape[3], out.dtype, out.device, mf,
+                              tuple(p.shape[1] for p in parts))
+        return out
+
+
+class _SinkBegin(nn.Module):
+    def __init__(self, sink):
+        super().__init__()
+        self.sink = sink
+
+    def forward(self, like):
+        return self.sink.begin(like)
+
+
+class _SinkSlot(nn.Module):
+    def __init__(self, sink, index):
+        super().__init__()
+        self.sink, self.index = sink, index
+
+    def forward(self, token):  # `token`: the result of `begin`, so that the slot is taken after it
+        return self.sink.slot(self.index)
+
+
+class _SinkFinish(nn.Module):
+    def __init__(self, sink):
+        super().__init__()
+        self.sink = sink
+
+    def forward(self, *parts):
+        return self.sink.finish(*parts)
+
+
+def _sink_parts(node, stack_names):
+    """(parts, indices of the parts a stack call produces for this node alone) of a channel
+    concatenation that has at least one such part, else None."""
+    from torch import fx
+
+    if not (node.op == "call_function" and node.target in (torch.cat, torch.concat)):
+        return None
+    args = list(node.args) + [node.kwargs.get("dim", 0)] if len(node.args) == 1 else list(node.args)
+    if not (len(args) == 2 and args[1] == 1 and isinstance(args[0], (list, tuple)) and len(args[0]) >= 2 and
+            all(isinstance(a, fx.Node) for a in args[0]) and set(node.kwargs) <= {"dim"} and
+            len(set(args[0])) == len(args[0])):
+        return None
+    parts = tuple(args[0])
+    mine = [i for i, a in enumerate(parts)
+            if a.op == "call_module" and a.target in stack_names and len(a.users) == 1 and "out" not in a.kwargs]
+    return (parts, mine) if mine else None
+
+
 def _concat_families(gm, stack_names):
     """Families of channel concatenations whose argument lists extend one another and whose
     results are read by stack calls only: [(cat nodes, smallest list first), ...]."""
@@ -604,6 +731,33 @@ def optimize_graph(model: nn.Module, min_layers: int = 1, concrete_args=None, sh
                 node.replace_all_uses_with(call)
                 gm.graph.erase_node(node)
             gm.concat_buffers.append(mod)
+    gm.concat_sinks = []
+    if share_concat_buffers:
+        names = {n for n, m in gm.named_modules() if isinstance(m, BrainSlugStack)}
+        order = {n: i for i, n in enumerate(gm.graph.nodes)}
+        for f, node in enumerate(list(gm.graph.nodes)):
+            found = _sink_parts(node, names)  # read now: earlier rewrites have replaced some of its parts
+            if found is None:
+                continue
+            parts, mine = found
+            sink = ConcatSink(len(parts), "always" if share_concat_buffers in (True, "always") else "capture")
+            gm.add_submodule(f"brainslug_sink_{f}", sink)
+            gm.add_submodule(f"brainslug_sink_{f}_begin", _SinkBegin(sink))
+            gm.add_submodule(f"brainslug_sink_{f}_finish", _SinkFinish(sink))
+            first = min((parts[i] for i in mine), key=lambda n: order[n])
+            with gm.graph.inserting_before(first):
+                begin = gm.graph.call_module(f"brainslug_sink_{f}_begin", args=(first.args[0],))
+            first.args = (begin, *first.args[1:])
+            for i in mine:
+                gm.add_submodule(f"brainslug_sink_{f}_slot_{i}", _SinkSlot(sink, i))
+                with gm.graph.inserting_before(parts[i]):
+                    slot = gm.graph.call_module(f"brainslug_sink_{f}_slot_{i}", args=(begin,))
+                parts[i].kwargs = dict(parts[i].kwargs, out=slot)
+            with gm.graph.inserting_after(node):
+                call = gm.graph.call_module(f"brainslug_sink_{f}_finish", args=parts)
+            node.replace_all_uses_with(call)
+            gm.graph.erase_node(node)
+            gm.concat_sinks.append(sink)
     gm.graph.lint()
     gm.recompile()
     gm.delete_all_unused_submodules()

@@ -399,6 +399,45 @@ def test_prefix_concat_shares_one_buffer_and_falls_back_when_unsure():
     assert out.requires_grad and pc.views_returned == before
 
 
+def test_concat_sink_protocol():
+    """begin / slot / finish: parts written into their slot arrive in place, the others are copied;
+    without a learnt shape (first pass), outside a capture by default, or for other shapes the
+    ordinary concatenation happens."""
+    a, b, c = torch.randn(2, 3, 4, 4), torch.randn(2, 2, 4, 4), torch.randn(2, 5, 4, 4)
+    want = torch.cat([a, b, c], 1)
+    sink = fe.ConcatSink(3, "always")
+    sink.begin(a)
+    assert sink.slot(1) is None                       # nothing learnt yet
+    assert torch.equal(sink.finish(a, b, c), want) and sink.known[6] == (3, 2, 5)
+    # CPU tensors never get a buffer (the stacks that would write into it need the GPU)
+    sink.begin(a)
+    assert sink.slot(0) is None and torch.equal(sink.finish(a, b, c), want)
+    # the buffer logic itself, with the device check lifted: write part 1 in place, pass the others
+    sink._buf = torch.empty(2, 10, 4, 4)
+    view = sink.slot(1)
+    assert view.shape == (2, 2, 4, 4) and view.data_ptr() == sink._buf[:, 3:5].data_ptr()
+    view.copy_(b)
+    out = sink.finish(a, view, c)
+    assert torch.equal(out, want) and sink.in_place == 1 and sink._buf is None
+    # parts of another shape than learnt: ordinary concatenation, and the new shape is learnt
+    sink._buf = torch.empty(2, 10, 4, 4)
+    d = torch.randn(2, 4, 4, 4)
+    assert torch.equal(sink.finish(a, d, c), torch.cat([a, d, c], 1)) and sink.known[6] == (3, 4, 5)
+    assert fe.ConcatSink(2).when == "capture"
+
+
+def test_concat_sinks_are_found_where_stacks_feed_a_concatenation():
+    torch.manual_seed(0)
+    g = fe.optimize_graph(zoo.inception_v3(0.125, 10).eval())
+    assert [s.n_parts for s in g.concat_sinks] == [4, 4, 4, 3, 4, 4, 4, 4, 3, 2, 2, 4, 2, 2, 4]
+    assert "torch.cat" not in str(g.graph)
+    assert len(fe.optimize_graph(zoo.squeezenet("1.1", 0.25, 10).eval(), lone_activations=True).concat_sinks) == 8
+    assert len(fe.optimize_graph(zoo.squeezenet("1.1", 0.25, 10).eval()).concat_sinks) == 0  # its parts are lone ReLUs
+    g = fe.optimize_graph(zoo.densenet(121, 0.25, 10).eval())                               # parts are convolutions
+    assert g.concat_sinks == [] and len(g.concat_buffers) == 4
+    assert fe.optimize_graph(zoo.inception_v3(0.125, 10).eval(), share_concat_buffers=False).concat_sinks == []
+
+
 def test_concat_families_are_rewritten_only_when_stacks_read_them():
     torch.manual_seed(0)
     g = fe.optimize_graph(zoo.densenet(121, 0.25, 10).eval())
@@ -531,6 +570,11 @@ def test_evaluated_architectures_rewritten_match_the_original(name, channels_las
     if name.startswith("densenet"):  # in either memory format
         shared = [c.views_returned for c in opt.concat_buffers]
         assert len(shared) == 4 and shared == [c.positions for c in opt.concat_buffers]
+    if name.startswith("inception") or name.startswith("squeezenet"):
+        # stacks that feed a concatenation wrote straight into it in the second pass (where the
+        # slice starts on a 16-byte boundary; the other parts were copied)
+        assert len(opt.concat_sinks) == (15 if name.startswith("inception") else 8)
+        assert sum(s.in_place for s in opt.concat_sinks) > 0
     used = set()
     for s in opt.optimized_stacks:
         for st in s._plans.values():
@@ -540,7 +584,7 @@ def test_evaluated_architectures_rewritten_match_the_original(name, channels_las
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("name", ["resnet18", "densenet121"])
+@pytest.mark.parametrize("name", ["resnet18", "densenet121", "inception_v3"])
 def test_rewritten_model_can_be_captured_in_a_hip_graph(name):
     """A rewritten model captured with torch.cuda.CUDAGraph: the stack calls allocate through
     torch only and launch on the capturing stream.  Replayed several times with eager work of
@@ -549,8 +593,9 @@ def test_rewritten_model_can_be_captured_in_a_hip_graph(name):
     torch.manual_seed(6)
     ref = zoo.randomize_batchnorm(ZOO[name](), 7).eval().cuda()
     opt = fe.optimize_graph(ref)
-    x = torch.randn(4, 3, 64, 64, device="cuda")
-    other = torch.randn(4, 3, 64, 64, device="cuda")
+    size = ZOO_INPUT.get(name, 64)
+    x = torch.randn(4, 3, size, size, device="cuda")
+    other = torch.randn(4, 3, size, size, device="cuda")
     with torch.no_grad():
         want = opt(x).clone()
         side = torch.cuda.Stream()
@@ -576,6 +621,8 @@ def test_rewritten_model_can_be_captured_in_a_hip_graph(name):
     # dense blocks share one concatenation buffer per block while captured, and only then
     assert all(c.views_returned == c.positions for c in opt.concat_buffers)
     assert len(opt.concat_buffers) == (4 if name == "densenet121" else 0)
+    assert len(opt.concat_sinks) == (15 if name == "inception_v3" else 0)
+    assert name != "inception_v3" or sum(s.in_place for s in opt.concat_sinks) > 0
     del graph
     for s in opt.optimized_stacks:
         s.close()
