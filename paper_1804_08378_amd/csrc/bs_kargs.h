@@ -211,7 +211,7 @@ struct NhwcK {
 // Outputs one lane produces per strip of a pooling phase, by column stride.  Two per lane for
 // stride 2 would make consecutive lanes read LDS four floats apart (no bank conflicts), but it
 // doubles the per-output address and predicate work; measured on MI355X four per lane is faster
-// for every BASELINE stack, so the rule is constant.  Planner, audit and kernels all use it.
+// for every benchmark stack, so the rule is constant.  Planner, audit and kernels all use it.
 #if defined(__HIPCC__)
 __host__ __device__
 #endif

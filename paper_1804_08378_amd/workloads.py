@@ -49,7 +49,7 @@ def activation(shape, seed: int, dtype: str = "f32") -> np.ndarray:
 
 
 def bn_params(channels: int, seed: int, eps: float = 1e-5) -> dict:
-    """BatchNorm inference parameters drawn as BASELINE config 0 states:
+    """BatchNorm inference parameters drawn as benchmark configuration 0 states:
     running_mean ~ N(0, sd 0.5), running_var ~ U(0.5, 2), gamma ~ U(0.5, 1.5),
     beta ~ N(0, sd 0.1)."""
     g = _rng(seed)
@@ -119,7 +119,7 @@ def num_residuals(layers) -> int:
 
 
 # ---------------------------------------------------------------------------
-# Named configurations (BASELINE configs 0-4).  Each entry: name -> builder
+# Named configurations (benchmark configurations 0-4).  Each entry: name -> builder
 # returning (layers, shape, dtypes).  `seed` feeds: input = seed, residual i =
 # seed + 1 + i, BN parameters of layer j = seed + 100 + j.
 # ---------------------------------------------------------------------------

@@ -431,8 +431,11 @@ def test_concat_sinks_are_found_where_stacks_feed_a_concatenation():
     g = fe.optimize_graph(zoo.inception_v3(0.125, 10).eval())
     assert [s.n_parts for s in g.concat_sinks] == [4, 4, 4, 3, 4, 4, 4, 4, 3, 2, 2, 4, 2, 2, 4]
     assert "torch.cat" not in str(g.graph)
+    # SqueezeNet's concatenated parts are lone ReLUs: left to PyTorch by default
+    assert len(fe.optimize_graph(zoo.squeezenet("1.1", 0.25, 10).eval()).concat_sinks) == 0
     assert len(fe.optimize_graph(zoo.squeezenet("1.1", 0.25, 10).eval(), lone_activations=True).concat_sinks) == 8
-    assert len(fe.optimize_graph(zoo.squeezenet("1.1", 0.25, 10).eval()).concat_sinks) == 0  # its parts are lone ReLUs
+    g = fe.optimize_graph(zoo.squeezenet("1.1", 0.25, 10).eval(), lone_activations="capture")
+    assert len(g.concat_sinks) == 8 and sum(isinstance(m, fe.CaptureOnlyStack) for m in g.modules()) == 24
     g = fe.optimize_graph(zoo.densenet(121, 0.25, 10).eval())                               # parts are convolutions
     assert g.concat_sinks == [] and len(g.concat_buffers) == 4
     assert fe.optimize_graph(zoo.inception_v3(0.125, 10).eval(), share_concat_buffers=False).concat_sinks == []
@@ -507,7 +510,12 @@ def test_chain_whose_input_is_overwritten_midway_stays_in_pytorch():
 def test_what_the_graph_front_end_leaves_alone():
     g = fe.optimize_graph(Hazards().eval(), lone_activations=True)
     assert [s.replaced for s in g.optimized_stacks] == [["BatchNorm2d", "add"], ["relu"]]
-    assert [s.replaced for s in fe.optimize_graph(Hazards().eval()).optimized_stacks] == [["BatchNorm2d", "add"]]
+    assert [s.replaced for s in fe.optimize_graph(Hazards().eval(), lone_activations=False).optimized_stacks] == \
+        [["BatchNorm2d", "add"]]
+    # "capture": a lone activation is a stack only while a HIP graph is being captured
+    g = fe.optimize_graph(Hazards().eval(), lone_activations="capture")
+    lone = [m for m in g.modules() if isinstance(m, fe.CaptureOnlyStack)]
+    assert len(lone) == 1 and torch.equal(lone[0](torch.tensor([-1.0, 2.0])), torch.tensor([0.0, 2.0]))
     text = str(g.graph)
     assert "relu_" in text and "max_pool2d" in text and text.count("operator.add") + text.count("_operator.add") >= 2
     x = torch.randn(1, 3, 4, 4)
@@ -632,9 +640,9 @@ def test_rewritten_model_can_be_captured_in_a_hip_graph(name):
 def test_capture_helper_replays_new_inputs():
     torch.manual_seed(8)
     ref = zoo.randomize_batchnorm(zoo.densenet(121, 0.25, 10), 9).eval().cuda()
-    opt = fe.optimize_graph(ref)
     xs = [torch.randn(2, 3, 64, 64, device="cuda") for _ in range(3)]
-    runner = fe.capture(opt, xs[0])
+    runner = fe.capture(ref, xs[0])  # rewrites the model first, with the settings that pay in a graph
+    opt = runner.model
     with torch.no_grad():
         for x in xs + xs[::-1]:
             got = runner(x).clone()

@@ -251,10 +251,10 @@ def test_indices_can_be_skipped():
     assert np.array_equal(out.cpu().numpy(), ref)
 
 
-# ------------------------------------------------------------------ full BASELINE sizes
+# ------------------------------------------------------------------ full benchmark sizes
 @pytest.mark.parametrize("name,dtype", [c for c in CASES if c[0] != "tiny"])
 def test_config_full_size(name, dtype):
-    """Whole tensors at the BASELINE sizes, in the launch configuration the benchmark
+    """Whole tensors at the benchmark sizes, in the launch configuration the benchmark
     times (automatic plan, indices off as in the bandwidth runs, then on)."""
     layers, x, res = wl.inputs_for(name, 0, dtype, indices=False)
     check(layers, x, res, dtype, f"{name}/full")
@@ -865,7 +865,7 @@ def test_channels_last_channel_slices(shape, dtype):
 @pytest.mark.parametrize("name,dtype", [("vgg_a", "f32"), ("resnet_stem", "bf16"), ("resnet_tail", "f16"),
                                         ("densenet_trans", "f32"), ("halo_stress", "f16")])
 def test_channels_last_configs_full_size(name, dtype):
-    """Whole tensors at the BASELINE sizes with channels-last plans, as `bench.py --nhwc` times them."""
+    """Whole tensors at the benchmark sizes with channels-last plans, as `bench.py --nhwc` times them."""
     layers, x, res = wl.inputs_for(name, 0, dtype, indices=False)
     _check_nhwc(layers, x, res, dtype, f"{name}/full")
 

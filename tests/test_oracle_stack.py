@@ -170,7 +170,7 @@ def test_ceil_mode_stack_depth_first_equals_breadth_first_and_torch():
 
 @pytest.mark.parametrize("name", wl.CONFIG_NAMES)
 def test_named_configs_vs_library_pipeline_f64(name):
-    """Every BASELINE configuration (batch cut to 2, planes cut to keep it quick) against
+    """Every benchmark configuration (batch cut to 2, planes cut to keep it quick) against
     torch's CPU operators evaluated in float64: fp32 tolerance of the benchmark spec."""
     layers, shape, _ = wl.build(name, seed=0, batch=2, indices=True)
     c = min(shape[1], 8)

@@ -62,7 +62,7 @@ def test_run_time_builds_compile_without_a_device():
             assert all(q["run_time_build"] == 1 for q in info["sequences"])
             assert bs.bs_stack_jit_check(st.handle) == n_kernels  # with and without index outputs
             st.close()
-    # the BASELINE stacks need none in float32 / bfloat16; in binary16, which has no signature
+    # the benchmark stacks need none in float32 / bfloat16; in binary16, which has no signature
     # tables compiled in, the ResNet stem's sliding-window kernel is a run-time build
     layers, shape, _ = wl.build("vgg_a")
     st = bs.Stack(layers, shape, "f32").plan(host_only=1, num_cus=256)
