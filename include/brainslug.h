@@ -333,6 +333,49 @@ BS_API bs_status bs_stack_check_buffers(const bs_stack *stack, const void *in, i
                                         const void *workspace, uint64_t workspace_bytes);
 
 /*
+ * Backward pass (Section 7 names training as the method's next step; Sections 2 and 3 fix the
+ * forward pass whose Jacobian this applies): plan it, once, after bs_stack_plan on the same
+ * device.  The stack is cut into stages (element-wise operations, then at most one pooling
+ * operation); stages whose output or max-pooling picks the backward pass needs get forward
+ * plans of their own (library-owned, freed by bs_stack_destroy or the next bs_stack_plan).
+ * Row-major (NCHW) plans only.  BatchNorm is the inference-mode layer (constant folded
+ * parameters): gradients are produced for the stack's input and its residual operands, none
+ * for BatchNorm parameters.
+ * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED (no device plan), BS_ERR_UNSUPPORTED (channels-last
+ *         plan), BS_ERR_DEVICE, BS_ERR_ALLOC, and those of bs_stack_plan for the stage plans.
+ */
+BS_API bs_status bs_stack_plan_backward(bs_stack *stack);
+/* Device bytes bs_stack_backward needs as workspace (0: none, or no backward plan). */
+BS_API uint64_t bs_stack_backward_workspace_bytes(const bs_stack *stack);
+/* Stages of the backward plan (-1 without one). */
+BS_API int32_t bs_stack_backward_num_stages(const bs_stack *stack);
+
+/*
+ * Enqueue the backward pass on `stream`: given the stack's input and residual operands of the
+ * forward pass and the gradient of a scalar with respect to the stack's output, compute its
+ * gradients with respect to the input and the residual operands -- grad_out times the
+ * Jacobian of the layer-by-layer forward pass, storage rounding taken as the identity.  The
+ * forward pass is not needed beforehand and nothing of it is kept: intermediate values and
+ * max-pooling picks are recomputed from `in` (first maximum in row-major window order, as in
+ * bs_stack_run).  ReLU passes the gradient where its input is > 0, clamp where
+ * lo <= input <= hi; average pooling uses the forward pass's divisor per window; overlapping
+ * windows add up.  Arithmetic is float32, each result rounded once to the stack dtype.
+ *   in, residuals    device, as in bs_stack_run (dense, the forward pass's values)
+ *   grad_out         device, dense, bs_stack_output_shape() elements of the stack dtype
+ *   grad_in          device, dense, the input's shape and dtype; NULL = not wanted
+ *   grad_residuals   host array of bs_stack_num_residuals() DEVICE pointers (shapes of the
+ *                    residual operands); the array or single entries may be NULL = not wanted
+ *   workspace        device, >= bs_stack_backward_workspace_bytes() (NULL allowed when 0)
+ * All device pointers 16-byte aligned; no output may overlap an input, the workspace or
+ * another output.  Never synchronises, never allocates.  The device of the plan must be current.
+ * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED (no backward plan), BS_ERR_DEVICE, BS_ERR_ALIGN,
+ *         BS_ERR_WORKSPACE, BS_ERR_ALIAS, BS_ERR_HIP.
+ */
+BS_API bs_status bs_stack_backward(const bs_stack *stack, const void *in, const void *const *residuals,
+                                   const void *grad_out, void *grad_in, void *const *grad_residuals,
+                                   void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
  * Compile, without loading them and without touching any device, all run-time builds the
  * current plan (device or host-only) asks for, for GPU architecture `arch` ("gfx950"; NULL =
  * "gfx950").  A way to check on a machine without a GPU that a stack's kernels build.

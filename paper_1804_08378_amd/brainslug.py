@@ -30,6 +30,8 @@ STATUS_NAMES = {
     9: "BS_ERR_HIP", 10: "BS_ERR_ALLOC", 11: "BS_ERR_RANGE", 12: "BS_ERR_ALIAS", 13: "BS_ERR_JIT", 14: "BS_ERR_DEVICE",
 }
 
+STATUS_BY_NAME = {v: k for k, v in STATUS_NAMES.items()}
+
 _f32p = C.POINTER(C.c_float)
 
 
@@ -100,6 +102,11 @@ _SIGNATURES = {
                                        C.c_int64, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
     "bs_stack_check_buffers": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.c_void_p,
                                          C.c_int64, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64]),
+    "bs_stack_plan_backward": (C.c_int, [C.c_void_p]),
+    "bs_stack_backward_workspace_bytes": (C.c_uint64, [C.c_void_p]),
+    "bs_stack_backward_num_stages": (C.c_int32, [C.c_void_p]),
+    "bs_stack_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
+                                    C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
     "bs_stack_jit_check": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]),
     "bs_jit_log": (C.c_char_p, []),
     "bs_status_string": (C.c_char_p, [C.c_int]),
@@ -325,6 +332,31 @@ def bs_stack_run(handle, in_ptr, residual_ptrs, out_ptr, index_ptrs, workspace_p
                                int(workspace_bytes), C.c_void_p(stream or None)), "bs_stack_run")
 
 
+def bs_stack_plan_backward(handle) -> None:
+    _check(load().bs_stack_plan_backward(C.c_void_p(handle)), "bs_stack_plan_backward")
+
+
+def bs_stack_backward_workspace_bytes(handle) -> int:
+    return int(load().bs_stack_backward_workspace_bytes(C.c_void_p(handle)))
+
+
+def bs_stack_backward_num_stages(handle) -> int:
+    return int(load().bs_stack_backward_num_stages(C.c_void_p(handle)))
+
+
+def bs_stack_backward(handle, in_ptr, residual_ptrs, grad_out_ptr, grad_in_ptr, grad_residual_ptrs, workspace_ptr,
+                      workspace_bytes, stream) -> None:
+    """All *_ptr arguments are integer device addresses (0 / None = NULL: that gradient is not wanted)."""
+    res = gres = None
+    if residual_ptrs:
+        res = (C.c_void_p * len(residual_ptrs))(*[C.c_void_p(p or None) for p in residual_ptrs])
+    if grad_residual_ptrs:
+        gres = (C.c_void_p * len(grad_residual_ptrs))(*[C.c_void_p(p or None) for p in grad_residual_ptrs])
+    _check(load().bs_stack_backward(C.c_void_p(handle), C.c_void_p(in_ptr or None), res, C.c_void_p(grad_out_ptr or None),
+                                    C.c_void_p(grad_in_ptr or None), gres, C.c_void_p(workspace_ptr or None),
+                                    int(workspace_bytes), C.c_void_p(stream or None)), "bs_stack_backward")
+
+
 def bs_stack_run_strided(handle, in_ptr, in_batch_stride, residual_ptrs, out_ptr, out_batch_stride,
                          index_ptrs, workspace_ptr, workspace_bytes, stream) -> None:
     """bs_stack_run on channel slices: batch strides in elements (0 = dense)."""
@@ -392,6 +424,8 @@ class Stack:
         self._workspace = None
         self._workspace_bytes = 0
         self._fast = None
+        self._bwd_workspace = None
+        self._bwd_planned = False
         self.layout = BS_LAYOUT_NCHW
 
     def close(self):
@@ -407,7 +441,46 @@ class Stack:
         self._workspace = None
         self._fast = None
         self._workspace_bytes = bs_stack_workspace_bytes(self.handle)
+        self._bwd_workspace = None
+        self._bwd_planned = False
         return self
+
+    def plan_backward(self):
+        """Plan the backward pass (after `plan`, row-major plans only)."""
+        bs_stack_plan_backward(self.handle)
+        self._bwd_planned = True
+        self._bwd_workspace = None
+        return self
+
+    def backward(self, x, residuals, grad_out, need_input_grad=True, need_residual_grads=None, stream=None):
+        """Enqueue the backward pass; returns (grad_x or None, [grad_residual or None, ...]).
+        `x` and `residuals` are the forward pass's operands, `grad_out` the gradient with respect
+        to its output; all dense tensors of the stack's dtype."""
+        import torch
+        if not getattr(self, "_bwd_planned", False):
+            self.plan_backward()
+        dt = self.torch_dtype()
+        if tuple(x.shape) != self.in_shape or x.dtype != dt or not x.is_contiguous():
+            raise ValueError("x must be a contiguous tensor of the stack's input shape and dtype")
+        if tuple(grad_out.shape) != self.out_shape or grad_out.dtype != dt or not grad_out.is_contiguous():
+            raise ValueError("grad_out must be a contiguous tensor of the stack's output shape and dtype")
+        if len(residuals) != self.n_res:
+            raise ValueError(f"the stack has {self.n_res} residual operands")
+        for i, r in enumerate(residuals):
+            if tuple(r.shape) != bs_stack_residual_shape(self.handle, i) or r.dtype != dt or not r.is_contiguous():
+                raise ValueError("residuals must be contiguous tensors of their Add layer's shape and the stack's dtype")
+        need_res = [True] * self.n_res if need_residual_grads is None else list(need_residual_grads)
+        gx = torch.empty_like(x) if need_input_grad else None
+        gres = [torch.empty_like(r) if need else None for r, need in zip(residuals, need_res)]
+        n = bs_stack_backward_workspace_bytes(self.handle)
+        if n and (self._bwd_workspace is None or self._bwd_workspace.numel() < n or self._bwd_workspace.device != x.device):
+            self._bwd_workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
+        ws = self._bwd_workspace if n else None
+        st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        bs_stack_backward(self.handle, x.data_ptr(), [r.data_ptr() for r in residuals], grad_out.data_ptr(),
+                          gx.data_ptr() if gx is not None else 0, [g.data_ptr() if g is not None else 0 for g in gres],
+                          ws.data_ptr() if ws is not None else 0, n, st)
+        return gx, gres
 
     def info(self) -> dict:
         p = bs_stack_plan_info(self.handle)

@@ -1,0 +1,286 @@
+// Backward pass of a stack (the paper's outlook, Section 7, names training as the next step;
+// the forward pass of Sections 2 and 3 fixes what it computes): the product of the upstream
+// gradient with the Jacobian of the layer-by-layer forward pass, with respect to the stack's
+// input and its residual operands.
+//
+// A fused forward pass keeps no intermediate tensor, so the backward pass recomputes what it
+// needs from the stack's input.  The stack is cut into stages, each a run of element-wise
+// operations followed by at most one pooling operation:
+//   * the input of every stage after the first, and the picks of every max pooling, are
+//     recomputed by running the stages as forward stacks of their own (the forward kernels of
+//     this library, index outputs switched on) into the workspace;
+//   * then one kernel per stage, last stage first, turns the gradient with respect to the
+//     stage's output into the gradient with respect to its input: it re-evaluates the stage's
+//     element-wise operations on the stored input to get their derivatives and gathers, for
+//     every input cell, the gradients of the pooling windows that hold it.
+// A stack of one stage without max pooling (BatchNorm -> Add -> ReLU, BatchNorm -> ReLU ->
+// AvgPool) needs no recomputation pass at all: input, upstream gradient in, gradients out.
+// Host code only; the kernel is in bs_backward.hip.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "bs_internal.h"
+
+using namespace bs;
+
+namespace {
+
+inline uint64_t numel(const int64_t *sh) { return (uint64_t)sh[0] * sh[1] * sh[2] * sh[3]; }
+inline uint64_t align256(uint64_t v) { return (v + 255u) & ~(uint64_t)255u; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool overlap(const void *a, uint64_t na, const void *b, uint64_t nb)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + nb && y < x + na;
+}
+
+// The stage's layers as a forward stack of their own, planned with the stack's options.
+bs_status make_forward(const bs_stack *s, BwdStage &g)
+{
+    std::vector<bs_layer_desc> descs((size_t)g.n_layers);
+    for (int32_t i = 0; i < g.n_layers; ++i) {
+        const Layer &L = s->layers[(size_t)(g.first_layer + i)];
+        bs_layer_desc d = L.desc;
+        d.gamma = L.gamma.data();
+        d.beta = L.beta.data();
+        d.running_mean = L.mean.data();
+        d.running_var = L.var.data();
+        d.return_indices = d.kind == BS_MAXPOOL ? 1 : 0;
+        // the output size is already fixed: ceil mode is recorded only where it adds a window
+        descs[(size_t)i] = d;
+    }
+    bs_stack *f = nullptr;
+    bs_status st = bs_stack_create(descs.data(), g.n_layers, g.in_shape, s->dtype, &f);
+    if (st != BS_OK) return st;
+    if (std::memcmp(f->out_shape, g.out_shape, sizeof g.out_shape) != 0) {
+        bs_stack_destroy(f);
+        return BS_ERR_SHAPE;
+    }
+    bs_plan_options o = s->opts;
+    o.host_only = 0;
+    o.breadth_first = 0;
+    o.force_variant = BS_VARIANT_AUTO;
+    st = bs_stack_plan(f, &o);
+    if (st != BS_OK) {
+        bs_stack_destroy(f);
+        return st;
+    }
+    g.forward = f;
+    return BS_OK;
+}
+
+}  // namespace
+
+namespace bs {
+
+void free_backward(bs_stack *s)
+{
+    if (!s || !s->backward) return;
+    for (BwdStage &g : s->backward->stages) bs_stack_destroy(g.forward);
+    delete s->backward;
+    s->backward = nullptr;
+}
+
+}  // namespace bs
+
+extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
+{
+    if (!stack) return BS_ERR_NULL;
+    if (!stack->planned || !stack->device_planned) return BS_ERR_NOT_PLANNED;
+    if (stack->opts.layout != BS_LAYOUT_NCHW) return BS_ERR_UNSUPPORTED;
+    if (current_device() != stack->device) return BS_ERR_DEVICE;
+    free_backward(stack);
+    BackwardPlan *plan = new (std::nothrow) BackwardPlan();
+    if (!plan) return BS_ERR_ALLOC;
+    stack->backward = plan;
+    bs_status st = BS_OK;
+    try {
+        // ---- operations -> stages
+        const int64_t N = stack->in_shape[0], C = stack->in_shape[1];
+        BwdStage cur;
+        int32_t adds = 0;
+        bool open = false;
+        auto begin = [&](const Op &op) {
+            cur = BwdStage();
+            cur.first_layer = op.layer;
+            const int64_t sh[4] = {N, C, op.in_h, op.in_w};
+            std::memcpy(cur.in_shape, sh, sizeof sh);
+            std::memcpy(cur.out_shape, sh, sizeof sh);
+            cur.k.C = (int32_t)C;
+            cur.k.H = cur.k.Ho = op.in_h;
+            cur.k.W = cur.k.Wo = op.in_w;
+            adds = 0;
+            open = true;
+        };
+        auto close = [&](int32_t last_layer) {
+            cur.n_layers = last_layer - cur.first_layer + 1;
+            plan->stages.push_back(cur);
+            open = false;
+        };
+        for (size_t i = 0; i < stack->ops.size(); ++i) {
+            const Op &op = stack->ops[i];
+            if (op.kind == OP_AVGNORM) continue;  // part of the average pooling before it
+            if (open && op_is_elementwise(op.kind) &&
+                (cur.k.n_ew >= K_BWD_EW || (op.kind == OP_ADD && adds >= K_MAX_RES)))
+                close(stack->ops[i - 1].layer);  // capacity of the argument block only
+            if (!open) begin(op);
+            if (op_is_elementwise(op.kind)) {
+                EwOp &e = cur.k.ew[cur.k.n_ew++];
+                e.kind = op.kind;
+                e.arg = op.param_off;
+                if (op.kind == OP_ADD) {
+                    e.arg = adds;
+                    cur.res_map[adds++] = op.res_slot;
+                    cur.n_res = adds;
+                }
+                continue;
+            }
+            PoolK &p = cur.k.pool;
+            p.kind = op.kind;
+            p.kh = op.kh; p.kw = op.kw; p.sh = op.sh; p.sw = op.sw; p.ph = op.ph; p.pw = op.pw;
+            p.count_include_pad = op.count_include_pad;
+            p.inv_kk = 1.0f / (float)(op.kh * op.kw);
+            p.idx_slot = -1;
+            cur.k.Ho = op.out_h;
+            cur.k.Wo = op.out_w;
+            cur.out_shape[2] = op.out_h;
+            cur.out_shape[3] = op.out_w;
+            close(op.layer);
+        }
+        if (open) close((int32_t)stack->layers.size() - 1);
+        if (plan->stages.empty()) st = BS_ERR_UNSUPPORTED;
+
+        // ---- launch geometry, forward stacks, workspace
+        const uint64_t es = dtype_size(stack->dtype);
+        const int32_t full = stack->dtype == BS_F32 ? 4 : 8;
+        const size_t S = plan->stages.size();
+        uint64_t off = 0;
+        for (size_t j = 0; j < S && st == BS_OK; ++j) {
+            BwdStage &g = plan->stages[j];
+            g.vec = g.k.W % full == 0 ? full : 1;
+            const uint64_t lanes = numel(g.in_shape) / (uint64_t)g.vec;
+            if (lanes > 0x7fffffffull) { st = BS_ERR_UNSUPPORTED; break; }
+            g.k.total = (uint32_t)lanes;
+            g.k.div_wv = make_fastdiv((uint32_t)(g.k.W / g.vec));
+            g.k.div_h = make_fastdiv((uint32_t)g.k.H);
+            g.k.div_c = make_fastdiv((uint32_t)g.k.C);
+            g.threads = 256;
+            g.grid = (int64_t)((lanes + 255) / 256);
+            const bool is_max = g.k.pool.kind == OP_MAXPOOL;
+            // the buffers are sized by these shapes: a stage must end where the next one begins
+            const int64_t *next = j + 1 < S ? plan->stages[j + 1].in_shape : stack->out_shape;
+            if (std::memcmp(g.out_shape, next, sizeof g.out_shape) != 0) { st = BS_ERR_SHAPE; break; }
+            if (j + 1 < S || is_max) st = make_forward(stack, g);
+            if (st != BS_OK) break;
+            if (j > 0) {
+                g.a_off = off;
+                off += align256(numel(g.in_shape) * es);
+                g.g_off = off;
+                off += align256(numel(g.in_shape) * es);
+            }
+            if (is_max) {
+                g.idx_off = off;
+                off += align256(numel(g.out_shape) * 4);
+            }
+            if (g.forward) plan->fwd_ws_bytes = std::max(plan->fwd_ws_bytes, g.forward->workspace_bytes);
+        }
+        if (st == BS_OK) {
+            if (plan->stages[S - 1].forward) {
+                plan->last_out_off = off;
+                off += align256(numel(plan->stages[S - 1].out_shape) * es);
+            }
+            plan->fwd_ws_off = off;
+            off += align256(plan->fwd_ws_bytes);
+            plan->workspace_bytes = off;
+        }
+    } catch (const std::bad_alloc &) {
+        st = BS_ERR_ALLOC;
+    }
+    if (st != BS_OK) free_backward(stack);
+    return st;
+}
+
+extern "C" uint64_t bs_stack_backward_workspace_bytes(const bs_stack *stack)
+{
+    return stack && stack->backward ? stack->backward->workspace_bytes : 0;
+}
+
+extern "C" int32_t bs_stack_backward_num_stages(const bs_stack *stack)
+{
+    return stack && stack->backward ? (int32_t)stack->backward->stages.size() : -1;
+}
+
+extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, const void *const *residuals,
+                                       const void *grad_out, void *grad_in, void *const *grad_residuals,
+                                       void *workspace, uint64_t workspace_bytes, void *stream)
+{
+    if (!stack || !in || !grad_out) return BS_ERR_NULL;
+    if (!stack->planned || !stack->device_planned || !stack->backward) return BS_ERR_NOT_PLANNED;
+    if (current_device() != stack->device) return BS_ERR_DEVICE;
+    const BackwardPlan &plan = *stack->backward;
+    if (stack->n_res > 0 && !residuals) return BS_ERR_NULL;
+    for (int32_t i = 0; i < stack->n_res; ++i)
+        if (!residuals[i]) return BS_ERR_NULL;
+
+    // ---- the caller's buffers: alignment, workspace, no output over an input or another output
+    const uint64_t es = dtype_size(stack->dtype);
+    struct Buf { const void *p; uint64_t bytes; };
+    Buf ins[2 + BS_MAX_RESIDUALS + 1], outs[1 + BS_MAX_RESIDUALS];
+    int n_in = 0, n_out = 0;
+    ins[n_in++] = Buf{in, numel(stack->in_shape) * es};
+    ins[n_in++] = Buf{grad_out, numel(stack->out_shape) * es};
+    for (int32_t i = 0; i < stack->n_res; ++i) ins[n_in++] = Buf{residuals[i], numel(stack->res_shape[i]) * es};
+    if (grad_in) outs[n_out++] = Buf{grad_in, numel(stack->in_shape) * es};
+    for (int32_t i = 0; i < stack->n_res; ++i)
+        if (grad_residuals && grad_residuals[i]) outs[n_out++] = Buf{grad_residuals[i], numel(stack->res_shape[i]) * es};
+    if (plan.workspace_bytes > 0) {
+        if (!workspace || workspace_bytes < plan.workspace_bytes) return BS_ERR_WORKSPACE;
+        ins[n_in++] = Buf{workspace, plan.workspace_bytes};
+    }
+    for (int i = 0; i < n_in; ++i)
+        if (!aligned16(ins[i].p)) return BS_ERR_ALIGN;
+    for (int i = 0; i < n_out; ++i) {
+        if (!aligned16(outs[i].p)) return BS_ERR_ALIGN;
+        for (int j = 0; j < n_in; ++j)
+            if (overlap(outs[i].p, outs[i].bytes, ins[j].p, ins[j].bytes)) return BS_ERR_ALIAS;
+        for (int j = 0; j < i; ++j)
+            if (overlap(outs[i].p, outs[i].bytes, outs[j].p, outs[j].bytes)) return BS_ERR_ALIAS;
+    }
+
+    char *ws = static_cast<char *>(workspace);
+    const size_t S = plan.stages.size();
+    // ---- recompute: the input of every stage after the first, the picks of every max pooling
+    for (size_t j = 0; j < S; ++j) {
+        const BwdStage &g = plan.stages[j];
+        if (!g.forward) continue;
+        const void *a = j == 0 ? in : ws + g.a_off;
+        void *out = j + 1 < S ? ws + plan.stages[j + 1].a_off : ws + plan.last_out_off;
+        const void *res[K_MAX_RES] = {nullptr, nullptr, nullptr, nullptr};
+        for (int32_t r = 0; r < g.n_res; ++r) res[r] = residuals[g.res_map[r]];
+        int32_t *idx[1] = {g.k.pool.kind == OP_MAXPOOL ? reinterpret_cast<int32_t *>(ws + g.idx_off) : nullptr};
+        const bs_status st = bs_stack_run(g.forward, a, res, out, g.forward->n_idx > 0 ? idx : nullptr,
+                                          ws + plan.fwd_ws_off, plan.fwd_ws_bytes, stream);
+        if (st != BS_OK) return st;
+    }
+    // ---- gradients, last stage first
+    for (size_t j = S; j-- > 0;) {
+        const BwdStage &g = plan.stages[j];
+        BwdK k = g.k;
+        k.a = j == 0 ? in : ws + g.a_off;
+        k.g_out = j + 1 == S ? grad_out : ws + plan.stages[j + 1].g_off;
+        k.g_in = j == 0 ? grad_in : ws + g.g_off;
+        k.idx = g.k.pool.kind == OP_MAXPOOL ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
+        k.params = stack->dev_params;
+        bool wanted = k.g_in != nullptr;
+        for (int32_t r = 0; r < g.n_res; ++r) {
+            k.res[r] = residuals[g.res_map[r]];
+            k.g_res[r] = grad_residuals ? grad_residuals[g.res_map[r]] : nullptr;
+            wanted = wanted || k.g_res[r] != nullptr;
+        }
+        if (!wanted) continue;  // first stage, and the caller asked for none of its gradients
+        const bs_status st = launch_backward_stage(k, stack->dtype, g.vec, g.grid, g.threads, stream);
+        if (st != BS_OK) return st;
+    }
+    return BS_OK;
+}

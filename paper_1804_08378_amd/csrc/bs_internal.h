@@ -65,6 +65,28 @@ struct Layer {
     int64_t in_shape[4] = {0, 0, 0, 0}, out_shape[4] = {0, 0, 0, 0};
 };
 
+// Backward pass: the stack cut into stages (element-wise operations, then at most one pooling
+// operation).  Stage j's input is recomputed by forward stacks over the stages before it.
+struct BwdStage {
+    int32_t first_layer = 0, n_layers = 0;
+    int64_t in_shape[4] = {0, 0, 0, 0}, out_shape[4] = {0, 0, 0, 0};
+    BwdK k{};
+    int32_t n_res = 0, res_map[K_MAX_RES] = {-1, -1, -1, -1};  // stack-wide residual numbers
+    int32_t vec = 1, threads = 256;
+    int64_t grid = 0;
+    bs_stack *forward = nullptr;  // this stage alone as a forward stack (null: its output and picks are not needed)
+    uint64_t a_off = 0;           // workspace offsets: the stage's input (stages >= 1),
+    uint64_t idx_off = 0;         // the picks of its max pooling,
+    uint64_t g_off = 0;           // the gradient with respect to its input (stages >= 1)
+};
+
+struct BackwardPlan {
+    std::vector<BwdStage> stages;
+    uint64_t workspace_bytes = 0;
+    uint64_t last_out_off = 0;    // output of the last stage's forward stack (only its picks are used)
+    uint64_t fwd_ws_off = 0, fwd_ws_bytes = 0;  // workspace of the forward stacks
+};
+
 struct Limits {
     uint64_t max_lds_bytes = 0;
     int32_t num_cus = 0;
@@ -94,6 +116,7 @@ struct bs_stack {
     uint64_t ws_half_bytes = 0;  // size of each of the two ping-pong halves
     uint64_t algorithmic_bytes = 0;
     bool jit_failed = false;  // a run-time build failed during this plan: plan again without
+    bs::BackwardPlan *backward = nullptr;  // bs_stack_plan_backward
 };
 
 namespace bs {
@@ -144,6 +167,9 @@ bool lds_precompiled(const LdsSeqK &k, int32_t dtype);
 bool lds_buildable(const LdsSeqK &k);
 std::string lds_expr(const LdsSeqK &k, int32_t dtype, bool want_idx);
 bs_status launch_lds(const LdsSeqK &k, int32_t dtype, int64_t grid, int32_t threads, uint64_t lds_bytes, void *stream);
+// bs_backward.cpp / bs_backward.hip
+void free_backward(bs_stack *s);
+bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream);
 // bs_trace.cpp
 bool trace_enabled();
 void trace_push_sequence(const Sequence &q, size_t index, size_t count);

@@ -202,6 +202,26 @@ struct NhwcK {
                       // div_wo then divides by the work-groups per image
 };
 
+// Backward pass of one stage: element-wise operations followed by at most one pooling
+// operation (pool.kind == 0: none).  Dense NCHW tensors only.
+constexpr int K_BWD_EW = 16;
+struct BwdK {
+    const void *a;        // the stage's input of the forward pass
+    const void *g_out;    // gradient with respect to the stage's output
+    void *g_in;           // gradient with respect to the stage's input (null: not wanted)
+    const int32_t *idx;   // max pooling: the forward pass's picks (cell index inside the input plane)
+    const float *params;
+    const void *res[K_MAX_RES];   // residual operands of the stage's Add operations, in order
+    void *g_res[K_MAX_RES];       // their gradients (null: not wanted)
+    int32_t n_ew;
+    EwOp ew[K_BWD_EW];    // Add: arg is unused, the n-th Add of the list uses res[n]
+    PoolK pool;
+    int32_t C, H, W, Ho, Wo;
+    uint32_t total;       // lanes with work = planes * H * (W / vec)
+    FastDiv div_wv;       // by W / vec
+    FastDiv div_h, div_c;
+};
+
 #if defined(__HIPCC__)
 #define BS_HD __host__ __device__ inline
 #else

@@ -1212,6 +1212,7 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (o.layout == BS_LAYOUT_NHWC && o.force_variant != BS_VARIANT_AUTO) return BS_ERR_PARAM;
 
     stack->planned = stack->device_planned = false;
+    free_backward(stack);  // it refers to this plan's operations and parameter table
     free_params(stack);
 
     Limits lim;

@@ -163,6 +163,7 @@ bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers, const i
 void bs_stack_destroy(bs_stack *stack)
 {
     if (!stack) return;
+    free_backward(stack);
     free_params(stack);
     delete stack;
 }

@@ -136,6 +136,22 @@ def test_plan_option_validation():
         bs.bs_stack_destroy(h)
 
 
+def test_backward_entry_points_without_a_device_plan():
+    """The backward pass needs the device plan (its parameter table and kernels): without one the
+    entry points say so and report no plan."""
+    h = bs.bs_stack_create([wl.bn_params(4, 0), wl.relu(), wl.maxpool(2, 2)], (1, 4, 8, 8), "f32")
+    try:
+        assert bs.bs_stack_backward_num_stages(h) == -1 and bs.bs_stack_backward_workspace_bytes(h) == 0
+        assert _status(bs.bs_stack_plan_backward, h) == 5           # not planned at all
+        bs.bs_stack_plan(h, host_only=1)
+        assert _status(bs.bs_stack_plan_backward, h) == 5           # host-only plan
+        assert _status(bs.bs_stack_backward, h, 16, None, 32, 48, None, 0, 0, 0) == 5
+        assert bs.bs_stack_backward_num_stages(h) == -1
+        assert _status(bs.bs_stack_plan_backward, None) == 1
+    finally:
+        bs.bs_stack_destroy(h)
+
+
 def test_size_limit_is_two_to_the_31_elements():
     """All index arithmetic is 32-bit: a tensor (input, output or intermediate) of 2^31 elements
     or more is refused at create, one just below is accepted and plans (host only)."""

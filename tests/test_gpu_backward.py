@@ -1,0 +1,212 @@
+"""Backward pass of the HIP path (bs_stack_plan_backward / bs_stack_backward through the C ABI)
+against the backward oracle on the same seeded inputs.
+
+Tolerance: the kernels accumulate in float32 and round once (the oracle in float64, unrounded):
+max|err| <= 1e-5 * max|ref| for float32 and 1e-2 * max|ref| for 16-bit storage, which also
+covers the 16-bit rounding of the gradients handed from stage to stage.  The decisions the
+gradient depends on (ReLU signs, max-pooling picks) are the forward pass's on both sides."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import backward as bw
+from paper_1804_08378_amd import brainslug as bs
+from paper_1804_08378_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2, "f16": 1e-2}
+TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+
+
+def _dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda", TORCH[dtype])
+
+
+def _inputs(layers, shape, seed, dtype):
+    x = wl.activation(shape, seed, dtype)
+    res = [wl.activation(s, seed + 1 + i, dtype) for i, s in enumerate(wl.residual_shapes(layers, shape))]
+    dy = wl.activation(wl.output_shape(layers, shape), seed + 50, dtype)
+    return x, res, dy
+
+
+def run_gpu(layers, x, res, dy, dtype, need_input=True, need_res=None, **opts):
+    st = bs.Stack(layers, x.shape, dtype).plan(**opts).plan_backward()
+    stages = bs.bs_stack_backward_num_stages(st.handle)
+    gx, gres = st.backward(_dev(x, dtype), [_dev(r, dtype) for r in res], _dev(dy, dtype), need_input, need_res)
+    torch.cuda.synchronize()
+    out = None if gx is None else gx.float().cpu().numpy()
+    outs = [None if g is None else g.float().cpu().numpy() for g in gres]
+    st.close()
+    return out, outs, stages
+
+
+def _close(got, ref, dtype, label):
+    assert got.shape == ref.shape, label
+    scale = float(np.abs(ref).max()) or 1.0
+    err = float(np.abs(got.astype(np.float64) - ref).max())
+    print(f"         {label}: max|err|={err:.3e} (bar {TOL[dtype] * scale:.3e})", flush=True)
+    assert np.isfinite(got).all(), label
+    assert err <= TOL[dtype] * scale, label
+
+
+def check(layers, shape, dtype, label, seed=0, **opts):
+    print(f"[backward] {label} shape={shape} dtype={dtype} opts={opts}", flush=True)
+    x, res, dy = _inputs(layers, shape, seed, dtype)
+    ref_x, ref_res = bw.backward_stack(layers, x, res, dy, dtype)
+    gx, gres, stages = run_gpu(layers, x, res, dy, dtype, **opts)
+    _close(gx, ref_x, dtype, label + " grad_x")
+    assert len(gres) == len(ref_res)
+    for i, (a, b) in enumerate(zip(gres, ref_res)):
+        _close(a, b, dtype, f"{label} grad_residual[{i}]")
+    return stages
+
+
+CASES = [(n, d) for n in wl.CONFIG_NAMES for d in wl.build(n)[2]]
+
+
+@pytest.mark.parametrize("name,dtype", CASES)
+def test_named_configurations(name, dtype):
+    layers, shape, _ = wl.build(name, 0, 2, False)
+    check(layers, shape, dtype, name)
+
+
+def _stacks(c):
+    return {
+        "bn_relu_max2": [wl.bn_params(c, 1), wl.relu(), wl.maxpool(2, 2, 0)],
+        "bn_relu_max3s2p1": [wl.bn_params(c, 2), wl.relu(), wl.maxpool(3, 2, 1)],
+        "bn_add_relu": [wl.bn_params(c, 3), wl.add(), wl.relu()],
+        "bn_relu_avg2": [wl.bn_params(c, 4), wl.relu(), wl.avgpool(2, 2)],
+        "halo_stress": [wl.bn_params(c, 5), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1),
+                        wl.bn_params(c, 6), wl.relu()],
+        "max_bn_relu_x3": sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 7 + i), wl.relu()] for i in range(3)), []),
+        "avg_nopad_div": [wl.relu(), wl.avgpool(3, 2, 1, False), wl.add(), wl.maxpool(2, 1, 0)],
+        "rect_windows": [wl.bn_params(c, 9), wl.maxpool((3, 2), (2, 1), (1, 0)), wl.avgpool((2, 3), (1, 2), (1, 1), True)],
+        "two_adds": [wl.add(), wl.bn_params(c, 10), wl.leaky_relu(0.1), wl.add(), wl.clamp(-0.5, 1.5)],
+        "ceil_avg": [wl.bn_params(c, 11), wl.avgpool(3, 2, 1, True, ceil_mode=True), wl.relu()],
+        "ceil_avg_nopad": [wl.avgpool(2, 2, 0, False, ceil_mode=True), wl.bn_params(c, 12)],
+        "ceil_max": [wl.leaky_relu(0.2), wl.maxpool(3, 2, 0, ceil_mode=True), wl.add(), wl.relu()],
+        "global_avg": [wl.bn_params(c, 13), wl.relu(), wl.avgpool((12, 16), (12, 16), 0)],
+        "global_max": [wl.bn_params(c, 14), wl.maxpool((12, 16), (12, 16), 0), wl.relu()],
+        "pool_first_then_add": [wl.maxpool(2, 2), wl.add(), wl.bn_params(c, 15), wl.relu(), wl.avgpool(2, 2), wl.add()],
+        "stride_gt_kernel": [wl.bn_params(c, 16), wl.maxpool(2, 3, 0), wl.avgpool(1, 2, 0)],
+    }
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("name", list(_stacks(3)))
+def test_small_stacks_vector_and_ragged_rows(name, dtype):
+    layers = _stacks(5)[name]
+    check(layers, (3, 5, 12, 16), dtype, name + "/vector rows")     # rows of whole 128-bit vectors
+    if not name.startswith("global"):
+        check(layers, (2, 5, 13, 11), dtype, name + "/ragged rows", seed=3)  # one cell per lane
+
+
+def test_long_lists_are_cut_into_stages():
+    c = 4
+    # 20 element-wise operations (more than one argument block holds), 6 Adds (more than one stage's residual slots)
+    layers = []
+    for i in range(6):
+        layers += [wl.bn_params(c, 20 + i), wl.add(), wl.leaky_relu(0.3)]
+    layers += [wl.relu(), wl.clamp(-1.0, 2.0)]
+    stages = check(layers, (2, c, 8, 8), "f32", "20 element-wise operations, 6 Adds")
+    assert stages >= 2
+    layers = layers + [wl.maxpool(2, 2)] + layers
+    check(layers, (2, c, 8, 8), "f32", "the same around a pooling operation")
+
+
+def test_gradients_that_are_not_wanted_are_not_written():
+    layers = [wl.bn_params(4, 1), wl.add(), wl.relu(), wl.maxpool(2, 2), wl.add(), wl.leaky_relu(0.1)]
+    shape = (2, 4, 8, 8)
+    x, res, dy = _inputs(layers, shape, 0, "f32")
+    ref_x, ref_res = bw.backward_stack(layers, x, res, dy)
+    gx, gres, _ = run_gpu(layers, x, res, dy, "f32", need_input=False, need_res=[True, False])
+    assert gx is None and gres[1] is None
+    _close(gres[0], ref_res[0], "f32", "only grad_residual[0]")
+    gx, gres, _ = run_gpu(layers, x, res, dy, "f32", need_input=True, need_res=[False, True])
+    assert gres[0] is None
+    _close(gx, ref_x, "f32", "grad_x")
+    _close(gres[1], ref_res[1], "f32", "grad_residual[1]")
+
+
+def test_single_stage_stacks_need_no_workspace_and_max_pooling_does():
+    st = bs.Stack([wl.bn_params(8, 1), wl.add(), wl.relu()], (2, 8, 8, 8), "f32").plan().plan_backward()
+    assert bs.bs_stack_backward_num_stages(st.handle) == 1 and bs.bs_stack_backward_workspace_bytes(st.handle) == 0
+    st.close()
+    st = bs.Stack([wl.bn_params(8, 1), wl.relu(), wl.avgpool(2, 2)], (2, 8, 8, 8), "f32").plan().plan_backward()
+    assert bs.bs_stack_backward_num_stages(st.handle) == 1 and bs.bs_stack_backward_workspace_bytes(st.handle) == 0
+    st.close()
+    st = bs.Stack([wl.bn_params(8, 1), wl.relu(), wl.maxpool(2, 2)], (2, 8, 8, 8), "f32").plan().plan_backward()
+    assert bs.bs_stack_backward_workspace_bytes(st.handle) >= 2 * 8 * 4 * 4 * 4  # the picks
+    st.close()
+
+
+def test_argument_errors():
+    layers = [wl.bn_params(8, 1), wl.relu(), wl.maxpool(2, 2)]
+    st = bs.Stack(layers, (2, 8, 8, 8), "f32").plan()
+    x = torch.zeros(2, 8, 8, 8, device="cuda")
+    dy = torch.zeros(2, 8, 4, 4, device="cuda")
+    gx = torch.empty_like(x)
+    with pytest.raises(bs.BrainSlugError) as e:  # no backward plan yet
+        bs.bs_stack_backward(st.handle, x.data_ptr(), [], dy.data_ptr(), gx.data_ptr(), [], 0, 0, 0)
+    assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_NOT_PLANNED"]
+    st.plan_backward()
+    n = bs.bs_stack_backward_workspace_bytes(st.handle)
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.bs_stack_backward(st.handle, x.data_ptr(), [], dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n - 1, 0)
+    assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_WORKSPACE"]
+    with pytest.raises(bs.BrainSlugError) as e:  # the gradient over the input
+        bs.bs_stack_backward(st.handle, x.data_ptr(), [], dy.data_ptr(), x.data_ptr(), [], ws.data_ptr(), n, 0)
+    assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_ALIAS"]
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.bs_stack_backward(st.handle, x.data_ptr() + 4, [], dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n, 0)
+    assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_ALIGN"]
+    with pytest.raises(bs.BrainSlugError) as e:
+        bs.bs_stack_backward(st.handle, 0, [], dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n, 0)
+    assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_NULL"]
+    # a new forward plan drops the backward plan
+    st.plan()
+    assert bs.bs_stack_backward_num_stages(st.handle) == -1
+    st.close()
+    st = bs.Stack(layers, (2, 8, 8, 8), "f16").plan(layout=bs.BS_LAYOUT_NHWC)
+    with pytest.raises(bs.BrainSlugError) as e:
+        st.plan_backward()
+    assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_UNSUPPORTED"]
+    st.close()
+
+
+def test_repeated_calls_give_identical_bits():
+    """A gather has one summation order: two runs agree bit for bit (no atomics anywhere)."""
+    layers = _stacks(6)["halo_stress"]
+    x, res, dy = _inputs(layers, (4, 6, 28, 28), 1, "f32")
+    a, _, _ = run_gpu(layers, x, res, dy, "f32")
+    b, _, _ = run_gpu(layers, x, res, dy, "f32")
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+@pytest.mark.parametrize("name,dtype", [("vgg_a", "f32"), ("vgg_c", "bf16"), ("resnet_tail", "f16"), ("halo_stress", "f32")])
+def test_benchmark_sizes_on_sampled_images(name, dtype):
+    """Whole tensors at the benchmark sizes on the GPU; images are independent, so the oracle checks
+    a sample of them (first, one inside, last) in full."""
+    layers, shape, _ = wl.build(name, 0, None, False)
+    print(f"[backward] {name} full size shape={shape} dtype={dtype}", flush=True)
+    td = TORCH[dtype]
+    g = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.randn(shape, device="cuda", generator=g).to(td)
+    out_shape = wl.output_shape(layers, shape)
+    dy = torch.randn(out_shape, device="cuda", generator=g).to(td)
+    res = [torch.randn(s, device="cuda", generator=g).to(td) for s in wl.residual_shapes(layers, shape)]
+    st = bs.Stack(layers, shape, dtype).plan().plan_backward()
+    gx, gres = st.backward(x, res, dy)
+    torch.cuda.synchronize()
+    for n in (0, shape[0] // 2 + 1, shape[0] - 1):
+        sl = slice(n, n + 1)
+        ref_x, ref_res = bw.backward_stack(layers, x[sl].float().cpu().numpy(), [r[sl].float().cpu().numpy() for r in res],
+                                           dy[sl].float().cpu().numpy(), dtype)
+        _close(gx[sl].float().cpu().numpy(), ref_x, dtype, f"{name} image {n} grad_x")
+        for i, r in enumerate(ref_res):
+            _close(gres[i][sl].float().cpu().numpy(), r, dtype, f"{name} image {n} grad_residual[{i}]")
+    st.close()
