@@ -316,6 +316,135 @@ def frontend_network(batch=32, reps=10,
                     % (batch, "channels_last" if channels_last else "NCHW"), "rows": rows}
 
 
+def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30):
+    """Backward pass of every benchmark configuration: `bs_stack_backward` (recompute from the stack
+    input, one gather kernel per stage) against the framework's autograd over the same layers run one by
+    one (its backward alone, on a retained graph; and forward + backward together on both sides).
+    GB/s counts the bytes a backward pass must move: input, residual operands and upstream gradient in,
+    gradients out."""
+    import numpy as np
+    import torch
+    import torch.nn.functional as F
+    from paper_1804_08378_amd import brainslug as bs
+    from paper_1804_08378_amd import workloads as wl
+
+    def torch_forward(layers, x, res):
+        cur, pending = x, list(res)
+        for l in layers:
+            k = l["kind"]
+            if k == "bn":
+                cur = F.batch_norm(cur, l["_mean"], l["_var"], l["_gamma"], l["_beta"], False, 0.0, l["eps"])
+            elif k == "relu":
+                cur = torch.relu(cur)
+            elif k == "add":
+                cur = cur + pending.pop(0)
+            elif k == "maxpool":
+                cur = F.max_pool2d(cur, l["k"], l["s"], l["p"])
+            else:
+                cur = F.avg_pool2d(cur, l["k"], l["s"], l["p"], False, l["count_include_pad"])
+        return cur
+
+    def timed(fn, n):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = []
+        for _ in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        t = [a.elapsed_time(b) for a, b in ev]
+        return sum(t) / len(t), min(t)
+
+    log("backward pass: bs_stack_backward vs the framework's autograd over the same layers")
+    log(f"{'config':<16}{'dtype':<6}{'stages':>7}{'MB':>8}{'us mean':>9}{'us min':>8}{'GB/s':>8}{'%peak':>7}"
+        f"{'autograd us':>12}{'speedup':>8}{'f+b us':>9}{'torch f+b':>10}{'speedup':>8}")
+    rows = []
+    for name in wl.CONFIG_NAMES:
+        for dt in wl.build(name)[2]:
+            layers, shape, _ = wl.build(name, 0, None, False)
+            tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dt]
+            es = 4 if dt == "f32" else 2
+            out_shape = wl.output_shape(layers, shape)
+            res_shapes = wl.residual_shapes(layers, shape)
+            numel = lambda sh: int(np.prod(sh))
+            nbytes = (2 * numel(shape) + 2 * sum(numel(r) for r in res_shapes) + numel(out_shape)) * es
+            sets = min(16, max(2, -(-min_rotation_bytes // nbytes)))
+            g = torch.Generator(device="cuda").manual_seed(0)
+            xs = [torch.randn(shape, device="cuda", generator=g).to(tdt) for _ in range(sets)]
+            rs = [[torch.randn(r, device="cuda", generator=g).to(tdt) for r in res_shapes] for _ in range(sets)]
+            dys = [torch.randn(out_shape, device="cuda", generator=g).to(tdt) for _ in range(sets)]
+            st = bs.Stack(layers, shape, dt).plan().plan_backward()
+            stages = bs.bs_stack_backward_num_stages(st.handle)
+            gx = [torch.empty_like(xs[0]) for _ in range(sets)]
+            gr = [[torch.empty_like(r) for r in rs[0]] for _ in range(sets)]
+            wsn = bs.bs_stack_backward_workspace_bytes(st.handle)
+            ws = torch.empty(max(wsn, 16), dtype=torch.uint8, device="cuda")
+            stream = torch.cuda.current_stream().cuda_stream
+            cur = [0]
+
+            def ours():
+                i = cur[0] = (cur[0] + 1) % sets
+                bs.bs_stack_backward(st.handle, xs[i].data_ptr(), [r.data_ptr() for r in rs[i]], dys[i].data_ptr(),
+                                     gx[i].data_ptr(), [t.data_ptr() for t in gr[i]], ws.data_ptr(), wsn, stream)
+
+            outs = [st.alloc_outputs("cuda", False)[0] for _ in range(sets)]
+
+            def ours_fb():
+                i = cur[0] = (cur[0] + 1) % sets
+                st.run(xs[i], rs[i], out=outs[i], indices=[])
+                bs.bs_stack_backward(st.handle, xs[i].data_ptr(), [r.data_ptr() for r in rs[i]], dys[i].data_ptr(),
+                                     gx[i].data_ptr(), [t.data_ptr() for t in gr[i]], ws.data_ptr(), wsn, stream)
+
+            ms, mn = timed(ours, steps)
+            ms_fb, _ = timed(ours_fb, steps)
+            # the framework: parameters on the device, one retained graph per buffer set
+            tl = []
+            for l in layers:
+                l = dict(l)
+                if l["kind"] == "bn":
+                    for k in ("mean", "var", "gamma", "beta"):
+                        l["_" + k] = torch.from_numpy(l[k]).cuda().to(tdt)
+                tl.append(l)
+            tsets = min(sets, 3)  # a retained graph holds every layer's output
+            graphs = []
+            for i in range(tsets):
+                leaves = [xs[i].detach().requires_grad_(True)] + [r.detach().requires_grad_(True) for r in rs[i]]
+                graphs.append((torch_forward(tl, leaves[0], leaves[1:]), leaves))
+
+            def torch_bwd():
+                i = cur[0] = (cur[0] + 1) % tsets
+                y, leaves = graphs[i]
+                torch.autograd.grad(y, leaves, dys[i], retain_graph=True)
+
+            ms_t, _ = timed(torch_bwd, max(5, steps // 3))
+            del graphs
+
+            def torch_fb():
+                i = cur[0] = (cur[0] + 1) % tsets
+                leaves = [xs[i].detach().requires_grad_(True)] + [r.detach().requires_grad_(True) for r in rs[i]]
+                torch.autograd.grad(torch_forward(tl, leaves[0], leaves[1:]), leaves, dys[i])
+
+            ms_tfb, _ = timed(torch_fb, max(5, steps // 3))
+            gbps = nbytes / (ms * 1e-3) / 1e9
+            row = {"config": name, "dtype": dt, "stages": stages, "MB": nbytes / 1e6, "us_mean": ms * 1e3, "us_min": mn * 1e3,
+                   "GBps": gbps, "pct_peak": 100 * gbps / HBM_PEAK_GBPS, "autograd_backward_us": ms_t * 1e3,
+                   "speedup_backward": ms_t / ms, "forward_backward_us": ms_fb * 1e3,
+                   "autograd_forward_backward_us": ms_tfb * 1e3, "speedup_forward_backward": ms_tfb / ms_fb}
+            rows.append(row)
+            log(f"{name:<16}{dt:<6}{stages:>7}{row['MB']:>8.1f}{row['us_mean']:>9.1f}{row['us_min']:>8.1f}{gbps:>8.0f}"
+                f"{row['pct_peak']:>7.1f}{row['autograd_backward_us']:>12.1f}{row['speedup_backward']:>8.2f}"
+                f"{row['forward_backward_us']:>9.1f}{row['autograd_forward_backward_us']:>10.1f}"
+                f"{row['speedup_forward_backward']:>8.2f}")
+            st.close()
+            del xs, rs, dys, gx, gr, outs, ws
+            torch.cuda.empty_cache()
+    return rows
+
+
 def deep_stacks(shape=(64, 64, 56, 56), counts=(1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 40)):
     """Section 5.1: networks of n blocks <MaxPool k3 s1 p1, BatchNorm, ReLU>, executed layer by
     layer and fused with at most 1 step, at most 5 steps, and unrestricted steps per sequence.
@@ -383,6 +512,8 @@ def main():
                          "frontend.optimize_graph()")
     ap.add_argument("--batch-scaling", action="store_true",
                     help="also time three whole networks at batch sizes 1 .. 128 (float32, NCHW)")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time the backward pass of every benchmark configuration against the framework's autograd (stderr)")
     ap.add_argument("--nhwc", action="store_true",
                     help="also time every configuration with channels-last (NHWC) tensors and plans")
     ap.add_argument("--frontend", action="store_true",
@@ -534,6 +665,11 @@ def main():
                     del sb
                     torch.cuda.empty_cache()
         out["all_configs"] = rows
+
+    if args.backward:
+        stacks = None
+        torch.cuda.empty_cache()
+        out["backward_configs"] = backward_configs(steps=min(args.steps, 30))
 
     if args.nhwc:
         stacks = None

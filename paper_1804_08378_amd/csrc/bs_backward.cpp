@@ -159,15 +159,19 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
         for (size_t j = 0; j < S && st == BS_OK; ++j) {
             BwdStage &g = plan->stages[j];
             g.vec = g.k.W % full == 0 ? full : 1;
-            const uint64_t lanes = numel(g.in_shape) / (uint64_t)g.vec;
+            const PoolK &p = g.k.pool;
+            // disjoint 2 x 2 windows that tile the plane: the kernel that owns whole windows
+            g.k.direct = p.kind != 0 && p.kh == 2 && p.kw == 2 && p.sh == 2 && p.sw == 2 && p.ph == 0 && p.pw == 0 &&
+                         g.k.H == 2 * g.k.Ho && g.k.W == 2 * g.k.Wo && g.vec == full;
+            const uint64_t lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 2 : 1);
             if (lanes > 0x7fffffffull) { st = BS_ERR_UNSUPPORTED; break; }
             g.k.total = (uint32_t)lanes;
             g.k.div_wv = make_fastdiv((uint32_t)(g.k.W / g.vec));
-            g.k.div_h = make_fastdiv((uint32_t)g.k.H);
+            g.k.div_h = make_fastdiv((uint32_t)(g.k.direct ? g.k.Ho : g.k.H));
             g.k.div_c = make_fastdiv((uint32_t)g.k.C);
             g.threads = 256;
             g.grid = (int64_t)((lanes + 255) / 256);
-            const bool is_max = g.k.pool.kind == OP_MAXPOOL;
+            const bool is_max = p.kind == OP_MAXPOOL && !g.k.direct;  // recorded picks needed
             // the buffers are sized by these shapes: a stage must end where the next one begins
             const int64_t *next = j + 1 < S ? plan->stages[j + 1].in_shape : stack->out_shape;
             if (std::memcmp(g.out_shape, next, sizeof g.out_shape) != 0) { st = BS_ERR_SHAPE; break; }
@@ -258,7 +262,8 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         void *out = j + 1 < S ? ws + plan.stages[j + 1].a_off : ws + plan.last_out_off;
         const void *res[K_MAX_RES] = {nullptr, nullptr, nullptr, nullptr};
         for (int32_t r = 0; r < g.n_res; ++r) res[r] = residuals[g.res_map[r]];
-        int32_t *idx[1] = {g.k.pool.kind == OP_MAXPOOL ? reinterpret_cast<int32_t *>(ws + g.idx_off) : nullptr};
+        const bool picks = g.k.pool.kind == OP_MAXPOOL && !g.k.direct;
+        int32_t *idx[1] = {picks ? reinterpret_cast<int32_t *>(ws + g.idx_off) : nullptr};
         const bs_status st = bs_stack_run(g.forward, a, res, out, g.forward->n_idx > 0 ? idx : nullptr,
                                           ws + plan.fwd_ws_off, plan.fwd_ws_bytes, stream);
         if (st != BS_OK) return st;
@@ -270,7 +275,7 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         k.a = j == 0 ? in : ws + g.a_off;
         k.g_out = j + 1 == S ? grad_out : ws + plan.stages[j + 1].g_off;
         k.g_in = j == 0 ? grad_in : ws + g.g_off;
-        k.idx = g.k.pool.kind == OP_MAXPOOL ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
+        k.idx = g.k.pool.kind == OP_MAXPOOL && !g.k.direct ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
         k.params = stack->dev_params;
         bool wanted = k.g_in != nullptr;
         for (int32_t r = 0; r < g.n_res; ++r) {

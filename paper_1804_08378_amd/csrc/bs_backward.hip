@@ -37,6 +37,119 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
     return 1.0f / (float)max(nr * nc, 1);
 }
 
+// Forward pass of the stage's element-wise list on R register rows of VEC cells each (row j
+// starts at element offset off[j]; all rows lie in channel c), collecting for every cell the
+// product t of the operations' derivatives and, for the n-th Add, the product r[n] of the
+// derivatives of the operations after it (0 for Adds the list does not have).
+template <int DT, int VEC, int R>
+BS_DEV int32_t ew_sweep(const BwdK &k, int32_t c, const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
+                        float (&r)[K_MAX_RES][R][VEC])
+{
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            t[j][e] = 1.0f;
+#pragma unroll
+            for (int n = 0; n < K_MAX_RES; ++n) r[n][j][e] = 0.0f;
+        }
+    int32_t adds = 0;
+#pragma clang loop unroll(disable)
+    for (int32_t q = 0; q < k.n_ew; ++q) {
+        const int32_t kind = k.ew[q].kind, arg = k.ew[q].arg;
+        if (kind == OP_ADD) {
+            Raw<DT, VEC> raw[R];
+#pragma unroll
+            for (int j = 0; j < R; ++j) raw[j] = load_raw<DT, VEC, true>(k.res[adds], off[j]);
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                float v[VEC];
+                unpack<DT, VEC>(raw[j], v);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[j][e] = round_store<DT>(x[j][e] + v[e]);
+            }
+            // from here on the residual's gradient collects the same factors as the input's
+#pragma unroll
+            for (int n = 0; n < K_MAX_RES; ++n)
+                if (n == adds) {
+#pragma unroll
+                    for (int j = 0; j < R; ++j)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) r[n][j][e] = 1.0f;
+                }
+            ++adds;
+            continue;
+        }
+        float f[R][VEC];  // d(output) / d(input) of this operation at x
+        if (kind == OP_BN) {
+            const float sc = k.params[arg + c], sh = k.params[arg + k.C + c];
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    f[j][e] = sc;
+                    x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc, sh));
+                }
+        } else if (kind == OP_RELU) {
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    f[j][e] = x[j][e] > 0.0f ? 1.0f : 0.0f;
+                    x[j][e] = __builtin_fmaxf(x[j][e], 0.0f);
+                }
+        } else if (kind == OP_LEAKY) {
+            const float slope = k.params[arg];
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    f[j][e] = x[j][e] > 0.0f ? 1.0f : slope;
+                    x[j][e] = round_store<DT>(x[j][e] > 0.0f ? x[j][e] : x[j][e] * slope);
+                }
+        } else {  // OP_CLAMP: the gradient passes where lo <= x <= hi
+            const float lo = k.params[arg], hi = k.params[arg + 1];
+#pragma unroll
+            for (int j = 0; j < R; ++j)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    f[j][e] = (x[j][e] >= lo && x[j][e] <= hi) ? 1.0f : 0.0f;
+                    x[j][e] = round_store<DT>(__builtin_fminf(__builtin_fmaxf(x[j][e], lo), hi));
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                t[j][e] *= f[j][e];
+#pragma unroll
+                for (int n = 0; n < K_MAX_RES; ++n) r[n][j][e] *= f[j][e];
+            }
+    }
+    return adds;
+}
+
+// Write grad_in = s * t and grad_residual[n] = s * r[n] for one register row.
+template <int DT, int VEC, int R>
+BS_DEV void store_row(const BwdK &k, int j, uint32_t off, int32_t adds, const float (&s)[VEC], const float (&t)[R][VEC],
+                      const float (&r)[K_MAX_RES][R][VEC])
+{
+    if (k.g_in) {
+        float v[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = s[e] * t[j][e];
+        store_elems<DT, VEC>(k.g_in, off, v);
+    }
+#pragma unroll
+    for (int n = 0; n < K_MAX_RES; ++n)
+        if (n < adds && k.g_res[n]) {
+            float v[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e] = s[e] * r[n][j][e];
+            store_elems<DT, VEC>(k.g_res[n], off, v);
+        }
+}
+
 template <int DT, int VEC>
 __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 {
@@ -53,69 +166,10 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
     const uint32_t off = rowi * (uint32_t)k.W + (uint32_t)iw0;  // < N*C*H*W: i < total, or 0
 
     // ---- 1. forward through the element-wise list, collecting derivative products
-    float x[VEC], t[VEC], r[K_MAX_RES][VEC];
-    unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x);
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-        t[e] = 1.0f;
-#pragma unroll
-        for (int n = 0; n < K_MAX_RES; ++n) r[n][e] = 0.0f;
-    }
-    int32_t adds = 0;
-#pragma clang loop unroll(disable)
-    for (int32_t j = 0; j < k.n_ew; ++j) {
-        const int32_t kind = k.ew[j].kind, arg = k.ew[j].arg;
-        if (kind == OP_ADD) {
-            float v[VEC];
-            unpack<DT, VEC>(load_raw<DT, VEC, true>(k.res[adds], off), v);
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) x[e] = round_store<DT>(x[e] + v[e]);
-            // from here on the residual's gradient collects the same factors as the input's
-#pragma unroll
-            for (int n = 0; n < K_MAX_RES; ++n)
-                if (n == adds) {
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) r[n][e] = 1.0f;
-                }
-            ++adds;
-            continue;
-        }
-        float f[VEC];  // d(output) / d(input) of this operation at x
-        if (kind == OP_BN) {
-            const float sc = k.params[arg + c], sh = k.params[arg + k.C + c];
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                f[e] = sc;
-                x[e] = round_store<DT>(__builtin_fmaf(x[e], sc, sh));
-            }
-        } else if (kind == OP_RELU) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                f[e] = x[e] > 0.0f ? 1.0f : 0.0f;
-                x[e] = __builtin_fmaxf(x[e], 0.0f);
-            }
-        } else if (kind == OP_LEAKY) {
-            const float slope = k.params[arg];
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                f[e] = x[e] > 0.0f ? 1.0f : slope;
-                x[e] = round_store<DT>(x[e] > 0.0f ? x[e] : x[e] * slope);
-            }
-        } else {  // OP_CLAMP: the gradient passes where lo <= x <= hi
-            const float lo = k.params[arg], hi = k.params[arg + 1];
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                f[e] = (x[e] >= lo && x[e] <= hi) ? 1.0f : 0.0f;
-                x[e] = round_store<DT>(__builtin_fminf(__builtin_fmaxf(x[e], lo), hi));
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            t[e] *= f[e];
-#pragma unroll
-            for (int n = 0; n < K_MAX_RES; ++n) r[n][e] *= f[e];
-        }
-    }
+    float x[1][VEC], t[1][VEC], r[K_MAX_RES][1][VEC];
+    unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x[0]);
+    const uint32_t offs[1] = {off};
+    const int32_t adds = ew_sweep<DT, VEC, 1>(k, c, offs, x, t, r);
 
     // ---- 2. gradient with respect to the list's output
     float s[VEC];
@@ -129,42 +183,103 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
         const int32_t oh_lo = th <= 0 ? 0 : (th + p.sh - 1) / p.sh;
         const int32_t oh_hi = min((ih + p.ph) / p.sh, k.Ho - 1);
         const uint32_t obase = plane * (uint32_t)(k.Ho * k.Wo);
+        // windows whose columns hold any of the lane's cells iw0 .. iw0 + VEC - 1: each is read once
+        // and handed to the cells it holds, so a cell still sums its windows in row-major order
+        const int32_t tw = iw0 + p.pw - p.kw + 1;
+        const int32_t ow_lo = tw <= 0 ? 0 : (tw + p.sw - 1) / p.sw;
+        const int32_t ow_hi = min((iw0 + VEC - 1 + p.pw) / p.sw, k.Wo - 1);
+        const int32_t cell0 = ih * k.W + iw0;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const int32_t iw = iw0 + e;
-            const int32_t tw = iw + p.pw - p.kw + 1;
-            const int32_t ow_lo = tw <= 0 ? 0 : (tw + p.sw - 1) / p.sw;
-            const int32_t ow_hi = min((iw + p.pw) / p.sw, k.Wo - 1);
-            const int32_t cell = ih * k.W + iw;
-            float acc = 0.0f;
-            for (int32_t oh = oh_lo; oh <= oh_hi; ++oh)
-                for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
-                    const uint32_t o = obase + (uint32_t)(oh * k.Wo + ow);  // 0 <= oh < Ho, 0 <= ow < Wo
-                    float g[1];
-                    unpack<DT, 1>(load_raw<DT, 1>(k.g_out, o), g);
-                    if (is_max) acc += k.idx[o] == cell ? g[0] : 0.0f;
-                    else acc += g[0] * bwd_avg_inv(p, k.H, k.W, oh, ow);
+        for (int e = 0; e < VEC; ++e) s[e] = 0.0f;
+        for (int32_t oh = oh_lo; oh <= oh_hi; ++oh)
+            for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
+                const uint32_t o = obase + (uint32_t)(oh * k.Wo + ow);  // 0 <= oh < Ho, 0 <= ow < Wo
+                float g[1];
+                unpack<DT, 1>(load_raw<DT, 1>(k.g_out, o), g);
+                if (is_max) {
+                    const int32_t d = k.idx[o] - cell0;  // the pick is one of the lane's cells if 0 <= d < VEC
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) s[e] += d == e ? g[0] : 0.0f;
+                } else {
+                    const float gi = g[0] * bwd_avg_inv(p, k.H, k.W, oh, ow);
+                    const int32_t w0 = ow * p.sw - p.pw - iw0;  // the window's columns, relative to the lane's first
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) s[e] += (e >= w0 && e < w0 + p.kw) ? gi : 0.0f;
                 }
-            s[e] = acc;
-        }
+            }
     }
 
     // ---- 3. results
-    if (!live) return;
-    if (k.g_in) {
-        float v[VEC];
+    if (live) store_row<DT, VEC, 1>(k, 0, off, adds, s, t, r);
+}
+
+// =============================================================================
+// bwd_direct2_kernel: a stage whose pooling has disjoint 2 x 2 windows that tile the plane
+// (2 x 2 / stride 2, no padding, even H, whole vectors per row): BatchNorm -> ReLU -> MaxPool of
+// the VGG stacks, the average pooling of a DenseNet transition.  Every input cell lies in exactly
+// one window, so a lane takes whole windows -- two input rows of VEC cells, VEC / 2 windows -- runs
+// the element-wise list on them, finds each max-pooling pick itself (first maximum in row-major
+// order, as the forward kernels do) and writes the gradients of all its cells.  No recorded
+// picks, no recomputation pass: the stage input and the gradient with respect to it move once.
+// =============================================================================
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
+{
+    constexpr int NO = VEC / 2;
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = i < k.total;
+    i = live ? i : 0u;
+    const uint32_t rowo = fdiv(i, k.div_wv);          // plane * Ho + oh
+    const uint32_t cv = i - rowo * k.div_wv.d;
+    const uint32_t plane = fdiv(rowo, k.div_h);       // div_h divides by Ho here
+    const uint32_t oh = rowo - plane * (uint32_t)k.Ho;
+    const uint32_t img = fdiv(plane, k.div_c);
+    const int32_t c = (int32_t)(plane - img * (uint32_t)k.C);
+    // rows 2 * oh and 2 * oh + 1 < H = 2 * Ho, columns cv * VEC .. + VEC - 1 < W
+    const uint32_t offs[2] = {(plane * (uint32_t)k.H + 2 * oh) * (uint32_t)k.W + cv * VEC,
+                              (plane * (uint32_t)k.H + 2 * oh + 1) * (uint32_t)k.W + cv * VEC};
+    const uint32_t out_off = rowo * (uint32_t)k.Wo + cv * NO;  // Wo = W / 2: NO outputs of row oh
+
+    const Raw<DT, VEC> a0 = load_raw<DT, VEC, true>(k.a, offs[0]), a1 = load_raw<DT, VEC, true>(k.a, offs[1]);
+    const Raw<DT, NO> gr = load_raw<DT, NO, true>(k.g_out, out_off);
+    float x[2][VEC], t[2][VEC], r[K_MAX_RES][2][VEC], g[NO];
+    unpack<DT, VEC>(a0, x[0]);
+    unpack<DT, VEC>(a1, x[1]);
+    unpack<DT, NO>(gr, g);
+    const int32_t adds = ew_sweep<DT, VEC, 2>(k, c, offs, x, t, r);
+
+    float s[2][VEC];
+    if (k.pool.kind == OP_MAXPOOL) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) v[e] = s[e] * t[e];
-        store_elems<DT, VEC>(k.g_in, off, v);
-    }
+        for (int j = 0; j < NO; ++j) {
+            float best = -INFINITY;
+            int pick = 0;
 #pragma unroll
-    for (int n = 0; n < K_MAX_RES; ++n)
-        if (n < adds && k.g_res[n]) {
-            float v[VEC];
+            for (int dh = 0; dh < 2; ++dh)
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) v[e] = s[e] * r[n][e];
-            store_elems<DT, VEC>(k.g_res[n], off, v);
+                for (int dw = 0; dw < 2; ++dw) {
+                    const bool more = x[dh][2 * j + dw] > best;
+                    best = more ? x[dh][2 * j + dw] : best;
+                    pick = more ? dh * 2 + dw : pick;
+                }
+#pragma unroll
+            for (int dh = 0; dh < 2; ++dh)
+#pragma unroll
+                for (int dw = 0; dw < 2; ++dw) s[dh][2 * j + dw] = pick == dh * 2 + dw ? g[j] : 0.0f;
         }
+    } else {
+#pragma unroll
+        for (int j = 0; j < NO; ++j) {
+            const float gi = g[j] * k.pool.inv_kk;  // every window lies inside the plane: the divisor is 4
+#pragma unroll
+            for (int dh = 0; dh < 2; ++dh)
+#pragma unroll
+                for (int dw = 0; dw < 2; ++dw) s[dh][2 * j + dw] = gi;
+        }
+    }
+    if (!live) return;
+    store_row<DT, VEC, 2>(k, 0, offs[0], adds, s[0], t, r);
+    store_row<DT, VEC, 2>(k, 1, offs[1], adds, s[1], t, r);
 }
 
 static void set_error(hipError_t e) { set_hip_error((int32_t)e); }
@@ -175,12 +290,29 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     const int32_t full = dtype == BS_F32 ? 4 : 8;
     // the launch must cover exactly the lanes the argument block describes
     if (grid < 1 || grid > 0x7fffffffll || threads != 256) return BS_ERR_UNSUPPORTED;
-    if ((vec != 1 && vec != full) || k.W % vec != 0 || (int64_t)k.div_wv.d * vec != k.W || (int64_t)k.div_h.d != k.H ||
-        (int64_t)k.div_c.d != k.C || (int64_t)grid * threads < (int64_t)k.total)
+    if ((vec != 1 && vec != full) || k.W % vec != 0 || (int64_t)k.div_wv.d * vec != k.W ||
+        (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_c.d != k.C || (int64_t)grid * threads < (int64_t)k.total)
         return BS_ERR_UNSUPPORTED;
     if (k.n_ew < 0 || k.n_ew > K_BWD_EW) return BS_ERR_UNSUPPORTED;
-    if (k.pool.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
     const dim3 g((uint32_t)grid), b((uint32_t)threads);
+    if (k.direct) {
+        const PoolK &p = k.pool;
+        // what the kernel assumes: 2 x 2 windows, stride 2, no padding, tiling the plane; whole vectors
+        if ((p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 2 || p.kw != 2 || p.sh != 2 || p.sw != 2 || p.ph != 0 ||
+            p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo || vec != full)
+            return BS_ERR_UNSUPPORTED;
+        if (dtype == BS_F32) bwd_direct2_kernel<DT_F32, 4><<<g, b, 0, st>>>(k);
+        else if (dtype == BS_BF16) bwd_direct2_kernel<DT_BF16, 8><<<g, b, 0, st>>>(k);
+        else if (dtype == BS_F16) bwd_direct2_kernel<DT_F16, 8><<<g, b, 0, st>>>(k);
+        else return BS_ERR_UNSUPPORTED;
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            set_error(e);
+            return BS_ERR_HIP;
+        }
+        return BS_OK;
+    }
+    if (k.pool.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
     if (dtype == BS_F32) {
         if (vec == 4) bwd_stage_kernel<DT_F32, 4><<<g, b, 0, st>>>(k);
         else bwd_stage_kernel<DT_F32, 1><<<g, b, 0, st>>>(k);

@@ -217,9 +217,11 @@ struct BwdK {
     EwOp ew[K_BWD_EW];    // Add: arg is unused, the n-th Add of the list uses res[n]
     PoolK pool;
     int32_t C, H, W, Ho, Wo;
-    uint32_t total;       // lanes with work = planes * H * (W / vec)
+    uint32_t total;       // lanes with work = planes * H * (W / vec); direct: planes * Ho * (W / vec)
     FastDiv div_wv;       // by W / vec
-    FastDiv div_h, div_c;
+    FastDiv div_h, div_c; // by H (direct: by Ho), by C
+    int32_t direct;       // 1: disjoint 2 x 2 windows that tile the plane; a lane owns whole windows and
+                          // finds the max-pooling picks itself (idx unused)
 };
 
 #if defined(__HIPCC__)

@@ -104,6 +104,29 @@ def test_small_stacks_vector_and_ragged_rows(name, dtype):
         check(layers, (2, 5, 13, 11), dtype, name + "/ragged rows", seed=3)  # one cell per lane
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_disjoint_two_by_two_windows(dtype):
+    c = 6
+    for pool in (wl.maxpool(2, 2), wl.avgpool(2, 2), wl.avgpool(2, 2, 0, False)):
+        layers = [wl.add(), wl.bn_params(c, 1), wl.leaky_relu(0.1), wl.add(), wl.relu(), pool, wl.bn_params(c, 2), wl.relu()]
+        check(layers, (3, c, 12, 16), dtype, f"2x2 windows that tile the plane ({pool['kind']})")
+        check(layers, (2, c, 13, 16), dtype, f"odd height: the general kernel ({pool['kind']})", seed=2)
+        check(layers, (2, c, 12, 12), dtype, f"rows of 12: {'whole vectors' if dtype == 'f32' else 'the general kernel'}", seed=4)
+    # ties: equal values in a window (after ReLU most windows of a negative plane are all zero)
+    layers = [wl.relu(), wl.maxpool(2, 2)]
+    x = -np.abs(wl.activation((2, c, 8, 16), 0, dtype))
+    x[:, :, ::3, ::5] = 1.0
+    dy = wl.activation((2, c, 4, 8), 1, dtype)
+    ref, _ = bw.backward_stack(layers, x, [], dy, dtype)
+    got, _, _ = run_gpu(layers, x, [], dy, dtype)
+    _close(got, ref, dtype, "ties")
+    # without the ReLU every tie goes to the first cell of the window
+    x = np.zeros((1, c, 8, 16), np.float32)
+    ref, _ = bw.backward_stack([wl.maxpool(2, 2)], x, [], dy[:1], dtype)
+    got, _, _ = run_gpu([wl.maxpool(2, 2)], x, [], dy[:1], dtype)
+    assert np.array_equal(got, ref.astype(np.float32))
+
+
 def test_long_lists_are_cut_into_stages():
     c = 4
     # 20 element-wise operations (more than one argument block holds), 6 Adds (more than one stage's residual slots)
@@ -138,13 +161,17 @@ def test_single_stage_stacks_need_no_workspace_and_max_pooling_does():
     st = bs.Stack([wl.bn_params(8, 1), wl.relu(), wl.avgpool(2, 2)], (2, 8, 8, 8), "f32").plan().plan_backward()
     assert bs.bs_stack_backward_num_stages(st.handle) == 1 and bs.bs_stack_backward_workspace_bytes(st.handle) == 0
     st.close()
+    # disjoint 2 x 2 windows: the kernel finds the picks itself
     st = bs.Stack([wl.bn_params(8, 1), wl.relu(), wl.maxpool(2, 2)], (2, 8, 8, 8), "f32").plan().plan_backward()
+    assert bs.bs_stack_backward_num_stages(st.handle) == 1 and bs.bs_stack_backward_workspace_bytes(st.handle) == 0
+    st.close()
+    st = bs.Stack([wl.bn_params(8, 1), wl.relu(), wl.maxpool(3, 2, 1)], (2, 8, 8, 8), "f32").plan().plan_backward()
     assert bs.bs_stack_backward_workspace_bytes(st.handle) >= 2 * 8 * 4 * 4 * 4  # the picks
     st.close()
 
 
 def test_argument_errors():
-    layers = [wl.bn_params(8, 1), wl.relu(), wl.maxpool(2, 2)]
+    layers = [wl.bn_params(8, 1), wl.relu(), wl.maxpool(3, 2, 1)]
     st = bs.Stack(layers, (2, 8, 8, 8), "f32").plan()
     x = torch.zeros(2, 8, 8, 8, device="cuda")
     dy = torch.zeros(2, 8, 4, 4, device="cuda")
