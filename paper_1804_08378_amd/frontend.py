@@ -131,8 +131,33 @@ def resolve_layers(layers: List[dict], shape) -> List[dict]:
     return out
 
 
+class _StackFunction(torch.autograd.Function):
+    """A stack as one node of the autograd graph: the forward pass keeps only the stack's operands
+    (no intermediate tensor exists to keep), the backward pass recomputes what it needs from them
+    (`bs_stack_backward`).  BatchNorm is the inference-mode layer, its parameters get no gradient."""
+
+    @staticmethod
+    def forward(ctx, module, x, *residuals):
+        st = module.plan_for(x.shape, x.dtype, False)
+        out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device)
+        st.run_unchecked(x, list(residuals), out, 0, 0)
+        ctx.save_for_backward(x, *residuals)
+        ctx.stack = st
+        return out
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        x, *residuals = ctx.saved_tensors
+        need = ctx.needs_input_grad  # (module, x, *residuals)
+        gx, gres = ctx.stack.backward(x, residuals, grad_out.contiguous(), need_input_grad=need[1],
+                                      need_residual_grads=list(need[2:]))
+        return (None, gx, *gres)
+
+
 class BrainSlugStack(nn.Module):
-    """A run of optimizable layers executed depth-first by the HIP library."""
+    """A run of optimizable layers executed depth-first by the HIP library.  Inference-mode layers
+    (BatchNorm with its running statistics); gradients flow through it to its input and its residual
+    operands when autograd records the call (fine-tuning with frozen BatchNorm layers)."""
 
     def __init__(self, modules: List[nn.Module], **plan_opts):
         descs = [layer_desc(m) for m in modules]
@@ -188,7 +213,8 @@ class BrainSlugStack(nn.Module):
         format or a channel slice of such a tensor (a concatenation buffer); when it does not fit
         (shape, type, alignment) it is ignored and a new tensor is returned."""
         if self.training:
-            raise RuntimeError("BrainSlugStack implements the inference forward pass only: call model.eval()")
+            raise RuntimeError("BrainSlugStack implements inference-mode layers only (BatchNorm with running "
+                               "statistics): call model.eval(); gradients still flow in that mode")
         if not x.is_cuda:
             raise RuntimeError("BrainSlugStack needs a tensor on the GPU")
         if x.dim() != 4:
@@ -202,6 +228,17 @@ class BrainSlugStack(nn.Module):
             return flat.view(x.shape)
         if self.channels is not None and x.shape[1] != self.channels:
             raise RuntimeError(f"expected {self.channels} channels, got {x.shape[1]}")
+        if torch.is_grad_enabled() and (x.requires_grad or any(r.requires_grad for r in residuals)):
+            # recorded by autograd: dense row-major operands (the backward pass has no channels-last
+            # or channel-slice kernels), a new output tensor (`out` is not used)
+            if len(residuals) != self.n_residuals:
+                raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
+            st = self.plan_for(x.shape, x.dtype, False)
+            for r, want in zip(residuals, st.res_shapes):
+                if r.shape != want or r.dtype != x.dtype or r.device != x.device:
+                    raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
+                                       f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
+            return _StackFunction.apply(self, x.contiguous(), *[r.contiguous() for r in residuals])
         with torch.no_grad():
             # a channels_last tensor stays channels_last: the stack is planned for that memory
             # order and its output is channels_last as well (what the convolutions around it use)
