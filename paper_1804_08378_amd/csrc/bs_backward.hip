@@ -150,7 +150,10 @@ BS_DEV void store_row(const BwdK &k, int j, uint32_t off, int32_t adds, const fl
         }
 }
 
-template <int DT, int VEC>
+// KH, KW, SH, SW: the pooling window and strides when they are compiled in (0: read from the
+// argument block).  With them the windows over a lane's cells are at most NOH x NOW, so all their
+// gradients and picks are requested at once instead of one dependent round trip per window.
+template <int DT, int VEC, int KH, int KW, int SH, int SW>
 __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -178,19 +181,53 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
         unpack<DT, VEC>(load_raw<DT, VEC, true>(k.g_out, off), s);
     } else {
         const bool is_max = p.kind == OP_MAXPOOL;
+        const int32_t kh = KH ? KH : p.kh, kw = KH ? KW : p.kw, sh = KH ? SH : p.sh, sw = KH ? SW : p.sw;
         // windows (oh, ow) whose rows hold ih: oh * sh - ph <= ih < oh * sh - ph + kh
-        const int32_t th = ih + p.ph - p.kh + 1;
-        const int32_t oh_lo = th <= 0 ? 0 : (th + p.sh - 1) / p.sh;
-        const int32_t oh_hi = min((ih + p.ph) / p.sh, k.Ho - 1);
+        const int32_t th = ih + p.ph - kh + 1;
+        const int32_t oh_lo = th <= 0 ? 0 : (th + sh - 1) / sh;
+        const int32_t oh_hi = min((ih + p.ph) / sh, k.Ho - 1);
         const uint32_t obase = plane * (uint32_t)(k.Ho * k.Wo);
         // windows whose columns hold any of the lane's cells iw0 .. iw0 + VEC - 1: each is read once
         // and handed to the cells it holds, so a cell still sums its windows in row-major order
-        const int32_t tw = iw0 + p.pw - p.kw + 1;
-        const int32_t ow_lo = tw <= 0 ? 0 : (tw + p.sw - 1) / p.sw;
-        const int32_t ow_hi = min((iw0 + VEC - 1 + p.pw) / p.sw, k.Wo - 1);
+        const int32_t tw = iw0 + p.pw - kw + 1;
+        const int32_t ow_lo = tw <= 0 ? 0 : (tw + sw - 1) / sw;
+        const int32_t ow_hi = min((iw0 + VEC - 1 + p.pw) / sw, k.Wo - 1);
         const int32_t cell0 = ih * k.W + iw0;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s[e] = 0.0f;
+        if constexpr (KH > 0) {
+            constexpr int NOH = (KH - 1) / SH + 1, NOW = (VEC + KW - 2) / SW + 1;
+            Raw<DT, 1> graw[NOH][NOW];
+            int32_t pick[NOH][NOW];
+#pragma unroll
+            for (int a = 0; a < NOH; ++a)
+#pragma unroll
+                for (int b = 0; b < NOW; ++b) {
+                    // windows beyond the range are read at a clamped (valid) position and not used
+                    const uint32_t o = obase + (uint32_t)(min(oh_lo + a, k.Ho - 1) * k.Wo + min(ow_lo + b, k.Wo - 1));
+                    graw[a][b] = load_raw<DT, 1>(k.g_out, o);
+                    pick[a][b] = is_max ? k.idx[o] : 0;
+                }
+#pragma unroll
+            for (int a = 0; a < NOH; ++a)
+#pragma unroll
+                for (int b = 0; b < NOW; ++b) {
+                    const int32_t oh = oh_lo + a, ow = ow_lo + b;
+                    const bool in = oh <= oh_hi && ow <= ow_hi;
+                    float g[1];
+                    unpack<DT, 1>(graw[a][b], g);
+                    if (is_max) {
+                        const int32_t d = pick[a][b] - cell0;
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) s[e] += (in && d == e) ? g[0] : 0.0f;
+                    } else {
+                        const float gi = g[0] * bwd_avg_inv(p, k.H, k.W, min(oh, k.Ho - 1), min(ow, k.Wo - 1));
+                        const int32_t w0 = ow * SW - p.pw - iw0;
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) s[e] += (in && e >= w0 && e < w0 + KW) ? gi : 0.0f;
+                    }
+                }
+        } else
         for (int32_t oh = oh_lo; oh <= oh_hi; ++oh)
             for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
                 const uint32_t o = obase + (uint32_t)(oh * k.Wo + ow);  // 0 <= oh < Ho, 0 <= ow < Wo
@@ -284,6 +321,17 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 
 static void set_error(hipError_t e) { set_hip_error((int32_t)e); }
 
+// The instance compiled for the stage's window, or the one that reads it from the argument block.
+template <int DT, int VEC>
+static void launch_stage(const BwdK &k, dim3 g, dim3 b, hipStream_t st)
+{
+    const PoolK &p = k.pool;
+    const bool w33 = p.kind != 0 && p.kh == 3 && p.kw == 3;
+    if (w33 && p.sh == 2 && p.sw == 2) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2><<<g, b, 0, st>>>(k);
+    else if (w33 && p.sh == 1 && p.sw == 1) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1><<<g, b, 0, st>>>(k);
+    else bwd_stage_kernel<DT, VEC, 0, 0, 0, 0><<<g, b, 0, st>>>(k);
+}
+
 bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream)
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -314,14 +362,14 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     }
     if (k.pool.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
     if (dtype == BS_F32) {
-        if (vec == 4) bwd_stage_kernel<DT_F32, 4><<<g, b, 0, st>>>(k);
-        else bwd_stage_kernel<DT_F32, 1><<<g, b, 0, st>>>(k);
+        if (vec == 4) launch_stage<DT_F32, 4>(k, g, b, st);
+        else launch_stage<DT_F32, 1>(k, g, b, st);
     } else if (dtype == BS_BF16) {
-        if (vec == 8) bwd_stage_kernel<DT_BF16, 8><<<g, b, 0, st>>>(k);
-        else bwd_stage_kernel<DT_BF16, 1><<<g, b, 0, st>>>(k);
+        if (vec == 8) launch_stage<DT_BF16, 8>(k, g, b, st);
+        else launch_stage<DT_BF16, 1>(k, g, b, st);
     } else if (dtype == BS_F16) {
-        if (vec == 8) bwd_stage_kernel<DT_F16, 8><<<g, b, 0, st>>>(k);
-        else bwd_stage_kernel<DT_F16, 1><<<g, b, 0, st>>>(k);
+        if (vec == 8) launch_stage<DT_F16, 8>(k, g, b, st);
+        else launch_stage<DT_F16, 1>(k, g, b, st);
     } else {
         return BS_ERR_UNSUPPORTED;
     }
