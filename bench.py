@@ -316,6 +316,67 @@ def frontend_network(batch=32, reps=10,
                     % (batch, "channels_last" if channels_last else "NCHW"), "rows": rows}
 
 
+def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50", "densenet121"),
+                      dtypes=("float32", "float16")):
+    """Fine-tuning step with frozen BatchNorm layers (eval mode, autograd on: the paper's outlook,
+    Section 7): forward pass, a scalar loss, backward pass to every convolution and linear weight.
+    PyTorch eager against the model rewritten by `optimize_graph`, whose stacks are single autograd
+    nodes that keep only their operands and recompute in `bs_stack_backward`.  Reports the time of a
+    step and the peak of allocated device memory during it."""
+    import torch
+    from paper_1804_08378_amd import frontend as fe
+    from paper_1804_08378_amd import zoo
+
+    make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "resnet18": lambda: zoo.resnet(18), "resnet50": lambda: zoo.resnet(50),
+            "densenet121": lambda: zoo.densenet(121), "inception_v3": lambda: zoo.inception_v3()}
+    rows = []
+    log("fine-tuning step (forward + backward, frozen BatchNorm), batch %d" % batch)
+    log(f"{'network':<14}{'dtype':<9}{'torch ms':>10}{'optimized ms':>14}{'speed-up %':>12}{'torch peak MB':>15}{'opt. peak MB':>14}"
+        f"{'memory %':>10}")
+    for name in names:
+        for dname in dtypes:
+            dtype = getattr(torch, dname)
+            torch.manual_seed(0)
+            ref = zoo.randomize_batchnorm(make[name]()).cuda().eval().to(dtype)
+            opt = fe.optimize_graph(ref)  # shares the parameters with `ref`
+            size = 299 if name.startswith("inception") else 224
+            xs = [torch.randn(batch, 3, size, size, device="cuda").to(dtype) for _ in range(2)]
+
+            def step(mod, x):
+                for p in mod.parameters():
+                    p.grad = None
+                loss = mod(x).float().square().mean()
+                loss.backward()
+
+            t, mem = {}, {}
+            for key, mod in (("ref", ref), ("opt", opt)):
+                for i in range(2):
+                    step(mod, xs[i % 2])
+                torch.cuda.synchronize()
+                base = torch.cuda.memory_allocated()
+                torch.cuda.reset_peak_memory_stats()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(reps):
+                    step(mod, xs[i % 2])
+                e1.record()
+                torch.cuda.synchronize()
+                t[key] = e0.elapsed_time(e1) / reps
+                mem[key] = (torch.cuda.max_memory_allocated() - base) / 1e6
+                for p in mod.parameters():
+                    p.grad = None
+            rows.append({"network": name, "dtype": dname, "torch_ms": round(t["ref"], 3), "optimized_ms": round(t["opt"], 3),
+                         "speedup_pct": round(100 * (t["ref"] / t["opt"] - 1), 1), "torch_peak_MB": round(mem["ref"], 1),
+                         "optimized_peak_MB": round(mem["opt"], 1), "memory_pct": round(100 * mem["opt"] / mem["ref"], 1)})
+            log(f"{name:<14}{dname:<9}{t['ref']:>10.3f}{t['opt']:>14.3f}{100 * (t['ref'] / t['opt'] - 1):>12.1f}"
+                f"{mem['ref']:>15.1f}{mem['opt']:>14.1f}{100 * mem['opt'] / mem['ref']:>10.1f}")
+            for st in opt.optimized_stacks:
+                st.close()
+            del ref, opt, xs
+            torch.cuda.empty_cache()
+    return {"what": "fine-tuning step (forward + backward, frozen BatchNorm), batch %d, NCHW" % batch, "rows": rows}
+
+
 def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30):
     """Backward pass of every benchmark configuration: `bs_stack_backward` (recompute from the stack
     input, one gather kernel per stage) against the framework's autograd over the same layers run one by
@@ -670,6 +731,7 @@ def main():
         stacks = None
         torch.cuda.empty_cache()
         out["backward_configs"] = backward_configs(steps=min(args.steps, 30))
+        out["fine_tuning"] = frontend_training()
 
     if args.nhwc:
         stacks = None
