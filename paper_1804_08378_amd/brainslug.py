@@ -429,7 +429,8 @@ class Stack:
         self.layout = BS_LAYOUT_NCHW
 
     def close(self):
-        if getattr(self, "handle", None):
+        # also runs as __del__, possibly while the interpreter shuts down and module globals are gone
+        if getattr(self, "handle", None) and bs_stack_destroy is not None:
             bs_stack_destroy(self.handle)
             self.handle = None
 

@@ -38,11 +38,11 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 }
 
 // Forward pass of the stage's element-wise list on R register rows of VEC cells each (row j
-// starts at element offset off[j]; all rows lie in channel c), collecting for every cell the
+// starts at element offset off[j] and lies in channel c[j]), collecting for every cell the
 // product t of the operations' derivatives and, for the n-th Add, the product r[n] of the
 // derivatives of the operations after it (0 for Adds the list does not have).
 template <int DT, int VEC, int R>
-BS_DEV int32_t ew_sweep(const BwdK &k, int32_t c, const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
+BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
                         float (&r)[K_MAX_RES][R][VEC])
 {
 #pragma unroll
@@ -82,13 +82,18 @@ BS_DEV int32_t ew_sweep(const BwdK &k, int32_t c, const uint32_t (&off)[R], floa
         }
         float f[R][VEC];  // d(output) / d(input) of this operation at x
         if (kind == OP_BN) {
-            const float sc = k.params[arg + c], sh = k.params[arg + k.C + c];
+            float sc[R], sh[R];
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                sc[j] = k.params[arg + c[j]];
+                sh[j] = k.params[arg + k.C + c[j]];
+            }
 #pragma unroll
             for (int j = 0; j < R; ++j)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    f[j][e] = sc;
-                    x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc, sh));
+                    f[j][e] = sc[j];
+                    x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc[j], sh[j]));
                 }
         } else if (kind == OP_RELU) {
 #pragma unroll
@@ -172,7 +177,8 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
     float x[1][VEC], t[1][VEC], r[K_MAX_RES][1][VEC];
     unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x[0]);
     const uint32_t offs[1] = {off};
-    const int32_t adds = ew_sweep<DT, VEC, 1>(k, c, offs, x, t, r);
+    const int32_t cs[1] = {c};
+    const int32_t adds = ew_sweep<DT, VEC, 1>(k, cs, offs, x, t, r);
 
     // ---- 2. gradient with respect to the list's output
     float s[VEC];
@@ -251,6 +257,46 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 }
 
 // =============================================================================
+// bwd_ew_kernel: a stage without pooling (BatchNorm -> Add -> ReLU of a residual block,
+// BatchNorm -> ReLU of a dense layer) whose planes are whole vectors.  The tensor is one run of
+// vectors; a work-group takes nthr * U consecutive ones, lane t the vectors t, t + nthr, ...:
+// U independent loads of every operand in flight per lane.
+// =============================================================================
+template <int DT, int VEC, int U>
+__global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
+{
+    const uint32_t nthr = blockDim.x;
+    const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
+    const uint32_t nvec = k.total;                      // vectors in the tensor
+    bool live[U];
+    uint32_t offs[U];
+    int32_t cs[U];
+    Raw<DT, VEC> ar[U], gr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t i = base + u * nthr;
+        live[u] = i < nvec;
+        i = live[u] ? i : 0u;
+        offs[u] = i * VEC;
+        // plane = i / hwv by way of the row: i / (W / VEC) / H
+        const uint32_t plane = fdiv(fdiv(i, k.div_wv), k.div_h);
+        cs[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
+        ar[u] = load_raw<DT, VEC, true>(k.a, offs[u]);
+        gr[u] = load_raw<DT, VEC, true>(k.g_out, offs[u]);
+    }
+    float x[U][VEC], t[U][VEC], r[K_MAX_RES][U][VEC], s[U][VEC];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        unpack<DT, VEC>(ar[u], x[u]);
+        unpack<DT, VEC>(gr[u], s[u]);
+    }
+    const int32_t adds = ew_sweep<DT, VEC, U>(k, cs, offs, x, t, r);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) store_row<DT, VEC, U>(k, u, offs[u], adds, s[u], t, r);
+}
+
+// =============================================================================
 // bwd_direct2_kernel: a stage whose pooling has disjoint 2 x 2 windows that tile the plane
 // (2 x 2 / stride 2, no padding, even H, whole vectors per row): BatchNorm -> ReLU -> MaxPool of
 // the VGG stacks, the average pooling of a DenseNet transition.  Every input cell lies in exactly
@@ -283,7 +329,8 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
     unpack<DT, VEC>(a0, x[0]);
     unpack<DT, VEC>(a1, x[1]);
     unpack<DT, NO>(gr, g);
-    const int32_t adds = ew_sweep<DT, VEC, 2>(k, c, offs, x, t, r);
+    const int32_t cs[2] = {c, c};
+    const int32_t adds = ew_sweep<DT, VEC, 2>(k, cs, offs, x, t, r);
 
     float s[2][VEC];
     if (k.pool.kind == OP_MAXPOOL) {
@@ -320,6 +367,8 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 }
 
 static void set_error(hipError_t e) { set_hip_error((int32_t)e); }
+
+constexpr int K_BWD_EW_U = 1;  // vectors per lane in bwd_ew_kernel (2 measured no faster in float32 and 70 % slower with 16-bit storage: registers)
 
 // The instance compiled for the stage's window, or the one that reads it from the argument block.
 template <int DT, int VEC>
@@ -361,6 +410,20 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         return BS_OK;
     }
     if (k.pool.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
+    if (k.pool.kind == 0 && vec == full) {
+        // no pooling, whole vectors: K_BWD_EW_U vectors per lane (the grid was sized for one per lane)
+        const dim3 gu((uint32_t)((grid + K_BWD_EW_U - 1) / K_BWD_EW_U));
+        if (dtype == BS_F32) bwd_ew_kernel<DT_F32, 4, K_BWD_EW_U><<<gu, b, 0, st>>>(k);
+        else if (dtype == BS_BF16) bwd_ew_kernel<DT_BF16, 8, K_BWD_EW_U><<<gu, b, 0, st>>>(k);
+        else if (dtype == BS_F16) bwd_ew_kernel<DT_F16, 8, K_BWD_EW_U><<<gu, b, 0, st>>>(k);
+        else return BS_ERR_UNSUPPORTED;
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            set_error(e);
+            return BS_ERR_HIP;
+        }
+        return BS_OK;
+    }
     if (dtype == BS_F32) {
         if (vec == 4) launch_stage<DT_F32, 4>(k, g, b, st);
         else launch_stage<DT_F32, 1>(k, g, b, st);
