@@ -317,7 +317,7 @@ def frontend_network(batch=32, reps=10,
 
 
 def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50", "densenet121"),
-                      dtypes=("float32", "float16")):
+                      dtypes=("float32", "float16"), channels_last=False):
     """Fine-tuning step with frozen BatchNorm layers (eval mode, autograd on: the paper's outlook,
     Section 7): forward pass, a scalar loss, backward pass to every convolution and linear weight.
     PyTorch eager against the model rewritten by `optimize_graph`, whose stacks are single autograd
@@ -330,7 +330,7 @@ def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50
     make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "resnet18": lambda: zoo.resnet(18), "resnet50": lambda: zoo.resnet(50),
             "densenet121": lambda: zoo.densenet(121), "inception_v3": lambda: zoo.inception_v3()}
     rows = []
-    log("fine-tuning step (forward + backward, frozen BatchNorm), batch %d" % batch)
+    log("fine-tuning step (forward + backward, frozen BatchNorm), batch %d%s" % (batch, ", channels_last" if channels_last else ""))
     log(f"{'network':<14}{'dtype':<9}{'torch ms':>10}{'optimized ms':>14}{'speed-up %':>12}{'torch peak MB':>15}{'opt. peak MB':>14}"
         f"{'memory %':>10}")
     for name in names:
@@ -338,9 +338,12 @@ def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50
             dtype = getattr(torch, dname)
             torch.manual_seed(0)
             ref = zoo.randomize_batchnorm(make[name]()).cuda().eval().to(dtype)
-            opt = fe.optimize_graph(ref)  # shares the parameters with `ref`
             size = 299 if name.startswith("inception") else 224
             xs = [torch.randn(batch, 3, size, size, device="cuda").to(dtype) for _ in range(2)]
+            if channels_last:
+                ref = ref.to(memory_format=torch.channels_last)
+                xs = [x.contiguous(memory_format=torch.channels_last) for x in xs]
+            opt = fe.optimize_graph(ref)  # shares the parameters with `ref`
 
             def step(mod, x):
                 for p in mod.parameters():
@@ -374,10 +377,11 @@ def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50
                 st.close()
             del ref, opt, xs
             torch.cuda.empty_cache()
-    return {"what": "fine-tuning step (forward + backward, frozen BatchNorm), batch %d, NCHW" % batch, "rows": rows}
+    return {"what": "fine-tuning step (forward + backward, frozen BatchNorm), batch %d, %s"
+                    % (batch, "channels_last" if channels_last else "NCHW"), "rows": rows}
 
 
-def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30):
+def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30, channels_last=False):
     """Backward pass of every benchmark configuration: `bs_stack_backward` (recompute from the stack
     input, one gather kernel per stage) against the framework's autograd over the same layers run one by
     one (its backward alone, on a retained graph; and forward + backward together on both sides).
@@ -420,7 +424,9 @@ def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30):
         t = [a.elapsed_time(b) for a, b in ev]
         return sum(t) / len(t), min(t)
 
-    log("backward pass: bs_stack_backward vs the framework's autograd over the same layers")
+    mf = torch.channels_last if channels_last else torch.contiguous_format
+    log("backward pass%s: bs_stack_backward vs the framework's autograd over the same layers" %
+        (", channels-last tensors" if channels_last else ""))
     log(f"{'config':<16}{'dtype':<6}{'stages':>7}{'MB':>8}{'us mean':>9}{'us min':>8}{'GB/s':>8}{'%peak':>7}"
         f"{'autograd us':>12}{'speedup':>8}{'f+b us':>9}{'torch f+b':>10}{'speedup':>8}")
     rows = []
@@ -435,13 +441,14 @@ def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30):
             nbytes = (2 * numel(shape) + 2 * sum(numel(r) for r in res_shapes) + numel(out_shape)) * es
             sets = min(16, max(2, -(-min_rotation_bytes // nbytes)))
             g = torch.Generator(device="cuda").manual_seed(0)
-            xs = [torch.randn(shape, device="cuda", generator=g).to(tdt) for _ in range(sets)]
-            rs = [[torch.randn(r, device="cuda", generator=g).to(tdt) for r in res_shapes] for _ in range(sets)]
-            dys = [torch.randn(out_shape, device="cuda", generator=g).to(tdt) for _ in range(sets)]
-            st = bs.Stack(layers, shape, dt).plan().plan_backward()
+            rnd = lambda sh: torch.randn(sh, device="cuda", generator=g).to(tdt).contiguous(memory_format=mf)
+            xs = [rnd(shape) for _ in range(sets)]
+            rs = [[rnd(r) for r in res_shapes] for _ in range(sets)]
+            dys = [rnd(out_shape) for _ in range(sets)]
+            st = bs.Stack(layers, shape, dt).plan(layout=1 if channels_last else 0).plan_backward()
             stages = bs.bs_stack_backward_num_stages(st.handle)
-            gx = [torch.empty_like(xs[0]) for _ in range(sets)]
-            gr = [[torch.empty_like(r) for r in rs[0]] for _ in range(sets)]
+            gx = [torch.empty_like(xs[0], memory_format=mf) for _ in range(sets)]
+            gr = [[torch.empty_like(r, memory_format=mf) for r in rs[0]] for _ in range(sets)]
             wsn = bs.bs_stack_backward_workspace_bytes(st.handle)
             ws = torch.empty(max(wsn, 16), dtype=torch.uint8, device="cuda")
             stream = torch.cuda.current_stream().cuda_stream
@@ -731,7 +738,9 @@ def main():
         stacks = None
         torch.cuda.empty_cache()
         out["backward_configs"] = backward_configs(steps=min(args.steps, 30))
+        out["backward_configs_channels_last"] = backward_configs(steps=min(args.steps, 30), channels_last=True)
         out["fine_tuning"] = frontend_training()
+        out["fine_tuning_channels_last"] = frontend_training(dtypes=("float16",), channels_last=True)
 
     if args.nhwc:
         stacks = None

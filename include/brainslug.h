@@ -338,11 +338,12 @@ BS_API bs_status bs_stack_check_buffers(const bs_stack *stack, const void *in, i
  * device.  The stack is cut into stages (element-wise operations, then at most one pooling
  * operation); stages whose output or max-pooling picks the backward pass needs get forward
  * plans of their own (library-owned, freed by bs_stack_destroy or the next bs_stack_plan).
- * Row-major (NCHW) plans only.  BatchNorm is the inference-mode layer (constant folded
+ * For the plan's memory layout (row-major or channels-last; all tensors of bs_stack_backward are
+ * then in that layout, dense).  BatchNorm is the inference-mode layer (constant folded
  * parameters): gradients are produced for the stack's input and its residual operands, none
  * for BatchNorm parameters.
- * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED (no device plan), BS_ERR_UNSUPPORTED (channels-last
- *         plan), BS_ERR_DEVICE, BS_ERR_ALLOC, and those of bs_stack_plan for the stage plans.
+ * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED (no device plan), BS_ERR_UNSUPPORTED (a tensor of 2^31
+ *         lanes), BS_ERR_DEVICE, BS_ERR_ALLOC, and those of bs_stack_plan for the stage plans.
  */
 BS_API bs_status bs_stack_plan_backward(bs_stack *stack);
 /* Device bytes bs_stack_backward needs as workspace (0: none, or no backward plan). */

@@ -447,7 +447,7 @@ class Stack:
         return self
 
     def plan_backward(self):
-        """Plan the backward pass (after `plan`, row-major plans only)."""
+        """Plan the backward pass (after `plan`; for the plan's memory layout)."""
         bs_stack_plan_backward(self.handle)
         self._bwd_planned = True
         self._bwd_workspace = None
@@ -456,23 +456,25 @@ class Stack:
     def backward(self, x, residuals, grad_out, need_input_grad=True, need_residual_grads=None, stream=None):
         """Enqueue the backward pass; returns (grad_x or None, [grad_residual or None, ...]).
         `x` and `residuals` are the forward pass's operands, `grad_out` the gradient with respect
-        to its output; all dense tensors of the stack's dtype."""
+        to its output; all dense tensors of the stack's dtype in the plan's memory layout (the
+        gradients come back in that layout)."""
         import torch
         if not getattr(self, "_bwd_planned", False):
             self.plan_backward()
         dt = self.torch_dtype()
-        if tuple(x.shape) != self.in_shape or x.dtype != dt or not x.is_contiguous():
-            raise ValueError("x must be a contiguous tensor of the stack's input shape and dtype")
-        if tuple(grad_out.shape) != self.out_shape or grad_out.dtype != dt or not grad_out.is_contiguous():
-            raise ValueError("grad_out must be a contiguous tensor of the stack's output shape and dtype")
+        mf = torch.channels_last if self.layout == BS_LAYOUT_NHWC else torch.contiguous_format
+        if tuple(x.shape) != self.in_shape or x.dtype != dt or not x.is_contiguous(memory_format=mf):
+            raise ValueError("x must be a dense tensor of the stack's input shape, dtype and memory layout")
+        if tuple(grad_out.shape) != self.out_shape or grad_out.dtype != dt or not grad_out.is_contiguous(memory_format=mf):
+            raise ValueError("grad_out must be a dense tensor of the stack's output shape, dtype and memory layout")
         if len(residuals) != self.n_res:
             raise ValueError(f"the stack has {self.n_res} residual operands")
         for i, r in enumerate(residuals):
-            if tuple(r.shape) != bs_stack_residual_shape(self.handle, i) or r.dtype != dt or not r.is_contiguous():
-                raise ValueError("residuals must be contiguous tensors of their Add layer's shape and the stack's dtype")
+            if tuple(r.shape) != bs_stack_residual_shape(self.handle, i) or r.dtype != dt or not r.is_contiguous(memory_format=mf):
+                raise ValueError("residuals must be dense tensors of their Add layer's shape, the stack's dtype and memory layout")
         need_res = [True] * self.n_res if need_residual_grads is None else list(need_residual_grads)
-        gx = torch.empty_like(x) if need_input_grad else None
-        gres = [torch.empty_like(r) if need else None for r, need in zip(residuals, need_res)]
+        gx = torch.empty_like(x, memory_format=mf) if need_input_grad else None
+        gres = [torch.empty_like(r, memory_format=mf) if need else None for r, need in zip(residuals, need_res)]
         n = bs_stack_backward_workspace_bytes(self.handle)
         if n and (self._bwd_workspace is None or self._bwd_workspace.numel() < n or self._bwd_workspace.device != x.device):
             self._bwd_workspace = torch.empty(n, dtype=torch.uint8, device=x.device)

@@ -88,7 +88,6 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
 {
     if (!stack) return BS_ERR_NULL;
     if (!stack->planned || !stack->device_planned) return BS_ERR_NOT_PLANNED;
-    if (stack->opts.layout != BS_LAYOUT_NCHW) return BS_ERR_UNSUPPORTED;
     if (current_device() != stack->device) return BS_ERR_DEVICE;
     free_backward(stack);
     BackwardPlan *plan = new (std::nothrow) BackwardPlan();
@@ -158,15 +157,28 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
         uint64_t off = 0;
         for (size_t j = 0; j < S && st == BS_OK; ++j) {
             BwdStage &g = plan->stages[j];
-            g.vec = g.k.W % full == 0 ? full : 1;
+            const bool nhwc = stack->opts.layout == BS_LAYOUT_NHWC;
             const PoolK &p = g.k.pool;
-            // disjoint 2 x 2 windows that tile the plane: the kernel that owns whole windows
-            g.k.direct = p.kind != 0 && p.kh == 2 && p.kw == 2 && p.sh == 2 && p.sw == 2 && p.ph == 0 && p.pw == 0 &&
-                         g.k.H == 2 * g.k.Ho && g.k.W == 2 * g.k.Wo && g.vec == full;
-            const uint64_t lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 2 : 1);
+            const bool tiles2x2 = p.kind != 0 && p.kh == 2 && p.kw == 2 && p.sh == 2 && p.sw == 2 && p.ph == 0 && p.pw == 0 &&
+                                  g.k.H == 2 * g.k.Ho && g.k.W == 2 * g.k.Wo;
+            uint64_t lanes;
+            g.k.nhwc = nhwc ? 1 : 0;
+            if (nhwc) {
+                // a lane per pixel (per window when 2 x 2 windows tile the plane) and channel vector
+                g.vec = g.k.C % full == 0 ? full : 1;
+                g.k.direct = tiles2x2 && g.vec == full;
+                lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 4 : 1);
+                g.k.div_wv = make_fastdiv((uint32_t)(g.k.C / g.vec));
+                g.k.div_w = make_fastdiv((uint32_t)(g.k.direct ? g.k.Wo : g.k.W));
+            } else {
+                g.vec = g.k.W % full == 0 ? full : 1;
+                // disjoint 2 x 2 windows that tile the plane: the kernel that owns whole windows
+                g.k.direct = tiles2x2 && g.vec == full;
+                lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 2 : 1);
+                g.k.div_wv = make_fastdiv((uint32_t)(g.k.W / g.vec));
+            }
             if (lanes > 0x7fffffffull) { st = BS_ERR_UNSUPPORTED; break; }
             g.k.total = (uint32_t)lanes;
-            g.k.div_wv = make_fastdiv((uint32_t)(g.k.W / g.vec));
             g.k.div_h = make_fastdiv((uint32_t)(g.k.direct ? g.k.Ho : g.k.H));
             g.k.div_c = make_fastdiv((uint32_t)g.k.C);
             g.threads = 256;

@@ -41,7 +41,9 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // starts at element offset off[j] and lies in channel c[j]), collecting for every cell the
 // product t of the operations' derivatives and, for the n-th Add, the product r[n] of the
 // derivatives of the operations after it (0 for Adds the list does not have).
-template <int DT, int VEC, int R>
+// CL: channels-last -- the VEC cells of a row are consecutive channels c[j] .. c[j] + VEC - 1 of one
+// pixel (all rows hold the same channels), so BatchNorm parameters are per-cell vectors.
+template <int DT, int VEC, int R, bool CL = false>
 BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
                         float (&r)[K_MAX_RES][R][VEC])
 {
@@ -82,19 +84,46 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
         }
         float f[R][VEC];  // d(output) / d(input) of this operation at x
         if (kind == OP_BN) {
-            float sc[R], sh[R];
+            if constexpr (CL) {
+                // tables start at multiples of 8 floats and c[0], C are multiples of VEC: 128-bit loads
+                float sc[VEC], sh[VEC];
+                if constexpr (VEC % 4 == 0) {
 #pragma unroll
-            for (int j = 0; j < R; ++j) {
-                sc[j] = k.params[arg + c[j]];
-                sh[j] = k.params[arg + k.C + c[j]];
-            }
+                    for (int q = 0; q < VEC / 4; ++q) {
+                        const float4 a = *reinterpret_cast<const float4 *>(k.params + arg + c[0] + 4 * q);
+                        const float4 b = *reinterpret_cast<const float4 *>(k.params + arg + k.C + c[0] + 4 * q);
+                        sc[4 * q] = a.x; sc[4 * q + 1] = a.y; sc[4 * q + 2] = a.z; sc[4 * q + 3] = a.w;
+                        sh[4 * q] = b.x; sh[4 * q + 1] = b.y; sh[4 * q + 2] = b.z; sh[4 * q + 3] = b.w;
+                    }
+                } else {
 #pragma unroll
-            for (int j = 0; j < R; ++j)
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    f[j][e] = sc[j];
-                    x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc[j], sh[j]));
+                    for (int e = 0; e < VEC; ++e) {
+                        sc[e] = k.params[arg + c[0] + e];
+                        sh[e] = k.params[arg + k.C + c[0] + e];
+                    }
                 }
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        f[j][e] = sc[e];
+                        x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc[e], sh[e]));
+                    }
+            } else {
+                float sc[R], sh[R];
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    sc[j] = k.params[arg + c[j]];
+                    sh[j] = k.params[arg + k.C + c[j]];
+                }
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        f[j][e] = sc[j];
+                        x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc[j], sh[j]));
+                    }
+            }
         } else if (kind == OP_RELU) {
 #pragma unroll
             for (int j = 0; j < R; ++j)
@@ -155,10 +184,12 @@ BS_DEV void store_row(const BwdK &k, int j, uint32_t off, int32_t adds, const fl
         }
 }
 
-// KH, KW, SH, SW: the pooling window and strides when they are compiled in (0: read from the
-// argument block).  With them the windows over a lane's cells are at most NOH x NOW, so all their
-// gradients and picks are requested at once instead of one dependent round trip per window.
-template <int DT, int VEC, int KH, int KW, int SH, int SW>
+// KH, KW, SH, SW, P: the pooling window, strides and padding (the same in both directions) when
+// they are compiled in (KH == 0: read from the argument block).  With them the windows over a
+// lane's cells are a fixed set -- NOH rows of NOW windows, and which cells each window holds is
+// known at compile time -- so a row's gradients and picks are requested at once instead of one
+// dependent round trip per window, and only the (window, cell) pairs that exist are summed.
+template <int DT, int VEC, int KH, int KW, int SH, int SW, int P>
 __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -202,37 +233,45 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s[e] = 0.0f;
         if constexpr (KH > 0) {
-            constexpr int NOH = (KH - 1) / SH + 1, NOW = (VEC + KW - 2) / SW + 1;
-            Raw<DT, 1> graw[NOH][NOW];
-            int32_t pick[NOH][NOW];
+            // iw0 is a multiple of VEC and VEC of SW (checked at launch), so the first window over the
+            // lane's cells is iw0 / SW + CQ with CQ = ceil((P - KW + 1) / SW), and window b of the row
+            // begins W0(b) = (CQ + b) * SW - P cells after iw0: compile-time.  Windows left of the plane
+            // (index < 0) or right of it are read at a clamped position and not used.
+            constexpr int Q = P - KW + 1;
+            constexpr int CQ = Q >= 0 ? (Q + SW - 1) / SW : -((-Q) / SW);
+            constexpr int NOH = (KH - 1) / SH + 1, NOW = (VEC - 1 + P) / SW - CQ + 1;
+            const int32_t ow0 = iw0 / SW + CQ;
 #pragma unroll
-            for (int a = 0; a < NOH; ++a)
+            for (int a = 0; a < NOH; ++a) {
+                Raw<DT, 1> graw[NOW];
+                int32_t pick[NOW];
+                const int32_t oh = oh_lo + a;
 #pragma unroll
                 for (int b = 0; b < NOW; ++b) {
-                    // windows beyond the range are read at a clamped (valid) position and not used
-                    const uint32_t o = obase + (uint32_t)(min(oh_lo + a, k.Ho - 1) * k.Wo + min(ow_lo + b, k.Wo - 1));
-                    graw[a][b] = load_raw<DT, 1>(k.g_out, o);
-                    pick[a][b] = is_max ? k.idx[o] : 0;
+                    const uint32_t o = obase + (uint32_t)(min(oh, k.Ho - 1) * k.Wo + min(max(ow0 + b, 0), k.Wo - 1));
+                    graw[b] = load_raw<DT, 1>(k.g_out, o);
+                    pick[b] = is_max ? k.idx[o] : 0;
                 }
 #pragma unroll
-            for (int a = 0; a < NOH; ++a)
-#pragma unroll
                 for (int b = 0; b < NOW; ++b) {
-                    const int32_t oh = oh_lo + a, ow = ow_lo + b;
-                    const bool in = oh <= oh_hi && ow <= ow_hi;
+                    const int32_t ow = ow0 + b;
+                    const bool in = oh <= oh_hi && ow >= 0 && ow < k.Wo;
                     float g[1];
-                    unpack<DT, 1>(graw[a][b], g);
+                    unpack<DT, 1>(graw[b], g);
+                    const int w0 = (CQ + b) * SW - P;  // a constant once the loop is unrolled
                     if (is_max) {
-                        const int32_t d = pick[a][b] - cell0;
+                        const int32_t d = pick[b] - cell0;
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e) s[e] += (in && d == e) ? g[0] : 0.0f;
+                        for (int e = 0; e < VEC; ++e)
+                            if (e >= w0 && e < w0 + KW) s[e] += (in && d == e) ? g[0] : 0.0f;
                     } else {
-                        const float gi = g[0] * bwd_avg_inv(p, k.H, k.W, min(oh, k.Ho - 1), min(ow, k.Wo - 1));
-                        const int32_t w0 = ow * SW - p.pw - iw0;
+                        const float gi = in ? g[0] * bwd_avg_inv(p, k.H, k.W, min(oh, k.Ho - 1), min(max(ow, 0), k.Wo - 1)) : 0.0f;
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e) s[e] += (in && e >= w0 && e < w0 + KW) ? gi : 0.0f;
+                        for (int e = 0; e < VEC; ++e)
+                            if (e >= w0 && e < w0 + KW) s[e] += gi;
                     }
                 }
+            }
         } else
         for (int32_t oh = oh_lo; oh <= oh_hi; ++oh)
             for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
@@ -366,6 +405,144 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
     store_row<DT, VEC, 2>(k, 1, offs[1], adds, s[1], t, r);
 }
 
+// =============================================================================
+// Channels-last tensors (N, H, W, C in memory).  A lane owns VEC consecutive channels of one
+// pixel: the same three steps as bwd_stage_kernel, with BatchNorm parameters as per-lane
+// vectors and a window's gradient and picks as one vector each (the VEC channels of the output
+// pixel), so every access of a wave is contiguous.
+// =============================================================================
+template <int VEC>
+BS_DEV void load_picks(const int32_t *idx, uint32_t off, int32_t (&v)[VEC])
+{
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            const int4 t = *reinterpret_cast<const int4 *>(idx + off + 4 * q);
+            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = idx[off + e];
+    }
+}
+
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = i < k.total;
+    i = live ? i : 0u;
+    const uint32_t pix = fdiv(i, k.div_wv);            // (n * H + ih) * W + iw
+    const uint32_t cv = i - pix * k.div_wv.d;
+    const uint32_t row = fdiv(pix, k.div_w);           // n * H + ih
+    const int32_t iw = (int32_t)(pix - row * (uint32_t)k.W);
+    const uint32_t n = fdiv(row, k.div_h);
+    const int32_t ih = (int32_t)(row - n * (uint32_t)k.H);
+    const int32_t c0 = (int32_t)(cv * VEC);
+    const uint32_t off = pix * (uint32_t)k.C + (uint32_t)c0;  // < N*H*W*C: i < total, or 0
+
+    float x[1][VEC], t[1][VEC], r[K_MAX_RES][1][VEC];
+    unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x[0]);
+    const uint32_t offs[1] = {off};
+    const int32_t cs[1] = {c0};
+    const int32_t adds = ew_sweep<DT, VEC, 1, true>(k, cs, offs, x, t, r);
+
+    float s[VEC];
+    const PoolK &p = k.pool;
+    if (p.kind == 0) {
+        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.g_out, off), s);
+    } else {
+        const bool is_max = p.kind == OP_MAXPOOL;
+        // windows (oh, ow) that hold the pixel
+        const int32_t th = ih + p.ph - p.kh + 1, tw = iw + p.pw - p.kw + 1;
+        const int32_t oh_lo = th <= 0 ? 0 : (th + p.sh - 1) / p.sh, ow_lo = tw <= 0 ? 0 : (tw + p.sw - 1) / p.sw;
+        const int32_t oh_hi = min((ih + p.ph) / p.sh, k.Ho - 1), ow_hi = min((iw + p.pw) / p.sw, k.Wo - 1);
+        const uint32_t obase = n * (uint32_t)(k.Ho * k.Wo);
+        const int32_t cell = ih * k.W + iw;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) s[e] = 0.0f;
+        for (int32_t oh = oh_lo; oh <= oh_hi; ++oh)
+            for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
+                // 0 <= oh < Ho, 0 <= ow < Wo: an output pixel; its VEC channels c0 .. c0 + VEC - 1
+                const uint32_t o = (obase + (uint32_t)(oh * k.Wo + ow)) * (uint32_t)k.C + (uint32_t)c0;
+                float g[VEC];
+                unpack<DT, VEC>(load_raw<DT, VEC>(k.g_out, o), g);
+                if (is_max) {
+                    int32_t pick[VEC];
+                    load_picks<VEC>(k.idx, o, pick);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) s[e] += pick[e] == cell ? g[e] : 0.0f;
+                } else {
+                    const float inv = bwd_avg_inv(p, k.H, k.W, oh, ow);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) s[e] += g[e] * inv;
+                }
+            }
+    }
+    if (live) store_row<DT, VEC, 1>(k, 0, off, adds, s, t, r);
+}
+
+// Disjoint 2 x 2 windows that tile the plane, channels-last: a lane owns VEC channels of one
+// window's four pixels (row-major window order: the order of the first-maximum rule).
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void bwd_direct2_nhwc_kernel(const BwdK k)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = i < k.total;
+    i = live ? i : 0u;
+    const uint32_t opix = fdiv(i, k.div_wv);           // (n * Ho + oh) * Wo + ow
+    const uint32_t cv = i - opix * k.div_wv.d;
+    const uint32_t orow = fdiv(opix, k.div_w);         // n * Ho + oh   (div_w divides by Wo here)
+    const uint32_t ow = opix - orow * (uint32_t)k.Wo;
+    const uint32_t n = fdiv(orow, k.div_h);            // div_h divides by Ho here
+    const uint32_t oh = orow - n * (uint32_t)k.Ho;
+    const int32_t c0 = (int32_t)(cv * VEC);
+    // input pixels (2 oh + dh, 2 ow + dw): H = 2 Ho, W = 2 Wo
+    const uint32_t p00 = (n * (uint32_t)k.H + 2 * oh) * (uint32_t)k.W + 2 * ow;
+    const uint32_t offs[4] = {p00 * (uint32_t)k.C + (uint32_t)c0, (p00 + 1) * (uint32_t)k.C + (uint32_t)c0,
+                              (p00 + (uint32_t)k.W) * (uint32_t)k.C + (uint32_t)c0,
+                              (p00 + (uint32_t)k.W + 1) * (uint32_t)k.C + (uint32_t)c0};
+    const uint32_t out_off = opix * (uint32_t)k.C + (uint32_t)c0;
+
+    Raw<DT, VEC> raw[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) raw[j] = load_raw<DT, VEC, true>(k.a, offs[j]);
+    const Raw<DT, VEC> gr = load_raw<DT, VEC, true>(k.g_out, out_off);
+    float x[4][VEC], t[4][VEC], r[K_MAX_RES][4][VEC], g[VEC];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) unpack<DT, VEC>(raw[j], x[j]);
+    unpack<DT, VEC>(gr, g);
+    const int32_t cs[4] = {c0, c0, c0, c0};
+    const int32_t adds = ew_sweep<DT, VEC, 4, true>(k, cs, offs, x, t, r);
+
+    float s[4][VEC];
+    if (k.pool.kind == OP_MAXPOOL) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            float best = -INFINITY;
+            int pick = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool more = x[j][e] > best;
+                best = more ? x[j][e] : best;
+                pick = more ? j : pick;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s[j][e] = pick == j ? g[e] : 0.0f;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float gi = g[e] * k.pool.inv_kk;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s[j][e] = gi;
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) store_row<DT, VEC, 4>(k, j, offs[j], adds, s[j], t, r);
+}
+
 static void set_error(hipError_t e) { set_hip_error((int32_t)e); }
 
 constexpr int K_BWD_EW_U = 1;  // vectors per lane in bwd_ew_kernel (2 measured no faster in float32 and 70 % slower with 16-bit storage: registers)
@@ -375,10 +552,11 @@ template <int DT, int VEC>
 static void launch_stage(const BwdK &k, dim3 g, dim3 b, hipStream_t st)
 {
     const PoolK &p = k.pool;
-    const bool w33 = p.kind != 0 && p.kh == 3 && p.kw == 3;
-    if (w33 && p.sh == 2 && p.sw == 2) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2><<<g, b, 0, st>>>(k);
-    else if (w33 && p.sh == 1 && p.sw == 1) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1><<<g, b, 0, st>>>(k);
-    else bwd_stage_kernel<DT, VEC, 0, 0, 0, 0><<<g, b, 0, st>>>(k);
+    // the compiled-in instances assume whole vectors per row and VEC a multiple of the stride
+    const bool w33p1 = p.kind != 0 && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && VEC > 1;
+    if (w33p1 && p.sh == 2 && p.sw == 2) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2, 1><<<g, b, 0, st>>>(k);
+    else if (w33p1 && p.sh == 1 && p.sw == 1) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1, 1><<<g, b, 0, st>>>(k);
+    else bwd_stage_kernel<DT, VEC, 0, 0, 0, 0, 0><<<g, b, 0, st>>>(k);
 }
 
 bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream)
@@ -387,11 +565,39 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     const int32_t full = dtype == BS_F32 ? 4 : 8;
     // the launch must cover exactly the lanes the argument block describes
     if (grid < 1 || grid > 0x7fffffffll || threads != 256) return BS_ERR_UNSUPPORTED;
+    if (k.n_ew < 0 || k.n_ew > K_BWD_EW) return BS_ERR_UNSUPPORTED;
+    const dim3 g((uint32_t)grid), b((uint32_t)threads);
+    if (k.nhwc) {
+        // a lane per (pixel or window, channel vector): the divisors must be the ones the kernels assume
+        if ((vec != 1 && vec != full) || k.C % vec != 0 || (int64_t)k.div_wv.d * vec != k.C ||
+            (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_w.d != (k.direct ? k.Wo : k.W) ||
+            (int64_t)grid * threads < (int64_t)k.total)
+            return BS_ERR_UNSUPPORTED;
+        const PoolK &p = k.pool;
+        if (k.direct && ((p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 2 || p.kw != 2 || p.sh != 2 || p.sw != 2 ||
+                         p.ph != 0 || p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo))
+            return BS_ERR_UNSUPPORTED;
+        if (!k.direct && p.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
+#define BS_LAUNCH_NHWC(DT, V)                                                          \
+    do {                                                                               \
+        if (k.direct) bwd_direct2_nhwc_kernel<DT, V><<<g, b, 0, st>>>(k);              \
+        else bwd_stage_nhwc_kernel<DT, V><<<g, b, 0, st>>>(k);                         \
+    } while (0)
+        if (dtype == BS_F32) { if (vec == 4) BS_LAUNCH_NHWC(DT_F32, 4); else BS_LAUNCH_NHWC(DT_F32, 1); }
+        else if (dtype == BS_BF16) { if (vec == 8) BS_LAUNCH_NHWC(DT_BF16, 8); else BS_LAUNCH_NHWC(DT_BF16, 1); }
+        else if (dtype == BS_F16) { if (vec == 8) BS_LAUNCH_NHWC(DT_F16, 8); else BS_LAUNCH_NHWC(DT_F16, 1); }
+        else return BS_ERR_UNSUPPORTED;
+#undef BS_LAUNCH_NHWC
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            set_error(e);
+            return BS_ERR_HIP;
+        }
+        return BS_OK;
+    }
     if ((vec != 1 && vec != full) || k.W % vec != 0 || (int64_t)k.div_wv.d * vec != k.W ||
         (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_c.d != k.C || (int64_t)grid * threads < (int64_t)k.total)
         return BS_ERR_UNSUPPORTED;
-    if (k.n_ew < 0 || k.n_ew > K_BWD_EW) return BS_ERR_UNSUPPORTED;
-    const dim3 g((uint32_t)grid), b((uint32_t)threads);
     if (k.direct) {
         const PoolK &p = k.pool;
         // what the kernel assumes: 2 x 2 windows, stride 2, no padding, tiling the plane; whole vectors

@@ -203,7 +203,7 @@ struct NhwcK {
 };
 
 // Backward pass of one stage: element-wise operations followed by at most one pooling
-// operation (pool.kind == 0: none).  Dense NCHW tensors only.
+// operation (pool.kind == 0: none).  Dense tensors only, row-major (NCHW) or channels-last.
 constexpr int K_BWD_EW = 16;
 struct BwdK {
     const void *a;        // the stage's input of the forward pass
@@ -222,6 +222,10 @@ struct BwdK {
     FastDiv div_h, div_c; // by H (direct: by Ho), by C
     int32_t direct;       // 1: disjoint 2 x 2 windows that tile the plane; a lane owns whole windows and
                           // finds the max-pooling picks itself (idx unused)
+    int32_t nhwc;         // 1: channels-last tensors.  A lane owns `vec` consecutive channels of one pixel (direct:
+                          // of one window's four pixels); total = pixels (direct: windows) * (C / vec), div_wv
+                          // divides by C / vec, div_h by H (direct: Ho), div_w by W (direct: Wo)
+    FastDiv div_w;
 };
 
 #if defined(__HIPCC__)

@@ -137,21 +137,22 @@ class _StackFunction(torch.autograd.Function):
     (`bs_stack_backward`).  BatchNorm is the inference-mode layer, its parameters get no gradient."""
 
     @staticmethod
-    def forward(ctx, module, x, *residuals):
-        st = module.plan_for(x.shape, x.dtype, False)
-        out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device)
+    def forward(ctx, module, nhwc, x, *residuals):
+        st = module.plan_for(x.shape, x.dtype, nhwc)
+        mf = torch.channels_last if nhwc else torch.contiguous_format
+        out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf)
         st.run_unchecked(x, list(residuals), out, 0, 0)
         ctx.save_for_backward(x, *residuals)
-        ctx.stack = st
+        ctx.stack, ctx.mf = st, mf
         return out
 
     @staticmethod
     def backward(ctx, grad_out):
         x, *residuals = ctx.saved_tensors
-        need = ctx.needs_input_grad  # (module, x, *residuals)
-        gx, gres = ctx.stack.backward(x, residuals, grad_out.contiguous(), need_input_grad=need[1],
-                                      need_residual_grads=list(need[2:]))
-        return (None, gx, *gres)
+        need = ctx.needs_input_grad  # (module, nhwc, x, *residuals)
+        gx, gres = ctx.stack.backward(x, residuals, grad_out.contiguous(memory_format=ctx.mf), need_input_grad=need[2],
+                                      need_residual_grads=list(need[3:]))
+        return (None, None, gx, *gres)
 
 
 class BrainSlugStack(nn.Module):
@@ -229,16 +230,19 @@ class BrainSlugStack(nn.Module):
         if self.channels is not None and x.shape[1] != self.channels:
             raise RuntimeError(f"expected {self.channels} channels, got {x.shape[1]}")
         if torch.is_grad_enabled() and (x.requires_grad or any(r.requires_grad for r in residuals)):
-            # recorded by autograd: dense row-major operands (the backward pass has no channels-last
-            # or channel-slice kernels), a new output tensor (`out` is not used)
+            # recorded by autograd: dense operands in the input's memory format (the backward pass
+            # has no channel-slice kernels: slices are copied), a new output tensor (`out` is not used)
             if len(residuals) != self.n_residuals:
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
-            st = self.plan_for(x.shape, x.dtype, False)
+            nhwc = not x.is_contiguous() and x.is_contiguous(memory_format=torch.channels_last)
+            mf = torch.channels_last if nhwc else torch.contiguous_format
+            st = self.plan_for(x.shape, x.dtype, nhwc)
             for r, want in zip(residuals, st.res_shapes):
                 if r.shape != want or r.dtype != x.dtype or r.device != x.device:
                     raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
                                        f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
-            return _StackFunction.apply(self, x.contiguous(), *[r.contiguous() for r in residuals])
+            return _StackFunction.apply(self, nhwc, x.contiguous(memory_format=mf),
+                                        *[r.contiguous(memory_format=mf) for r in residuals])
         with torch.no_grad():
             # a channels_last tensor stays channels_last: the stack is planned for that memory
             # order and its output is channels_last as well (what the convolutions around it use)

@@ -770,6 +770,12 @@ def test_stack_under_autograd_keeps_only_its_operands():
     x2 = x.detach().clone().requires_grad_(True)
     (g2,) = torch.autograd.grad(reference(x2).sum(), [x2])
     assert (gx - g2).abs().max().item() <= 1e-5 * g2.abs().max().item()
+    # channels_last operands: the stack, its output and its gradients stay channels_last
+    xc = x.detach().clone().contiguous(memory_format=torch.channels_last).requires_grad_(True)
+    yc = stack(xc)
+    assert yc.is_contiguous(memory_format=torch.channels_last) and torch.equal(yc, y)
+    (gc,) = torch.autograd.grad(yc.sum(), [xc])
+    assert gc.is_contiguous(memory_format=torch.channels_last) and torch.equal(gc, gx)
     # no gradient wanted: the plain path, nothing recorded
     with torch.no_grad():
         assert not stack(x).requires_grad
