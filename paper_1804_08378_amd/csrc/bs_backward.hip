@@ -43,9 +43,10 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // derivatives of the operations after it (0 for Adds the list does not have).
 // CL: channels-last -- the VEC cells of a row are consecutive channels c[j] .. c[j] + VEC - 1 of one
 // pixel (all rows hold the same channels), so BatchNorm parameters are per-cell vectors.
-template <int DT, int VEC, int R, bool CL = false>
+// NR: residual gradients kept (K_MAX_RES, or 0 for a stage without Add: no registers for them).
+template <int DT, int VEC, int R, bool CL = false, int NR = K_MAX_RES>
 BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
-                        float (&r)[K_MAX_RES][R][VEC])
+                        float (&r)[NR ? NR : 1][R][VEC])
 {
 #pragma unroll
     for (int j = 0; j < R; ++j)
@@ -53,13 +54,14 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
         for (int e = 0; e < VEC; ++e) {
             t[j][e] = 1.0f;
 #pragma unroll
-            for (int n = 0; n < K_MAX_RES; ++n) r[n][j][e] = 0.0f;
+            for (int n = 0; n < NR; ++n) r[n][j][e] = 0.0f;
         }
     int32_t adds = 0;
 #pragma clang loop unroll(disable)
     for (int32_t q = 0; q < k.n_ew; ++q) {
         const int32_t kind = k.ew[q].kind, arg = k.ew[q].arg;
         if (kind == OP_ADD) {
+            if constexpr (NR == 0) continue;  // instances for stages without Add (chosen at launch): nothing to read
             Raw<DT, VEC> raw[R];
 #pragma unroll
             for (int j = 0; j < R; ++j) raw[j] = load_raw<DT, VEC, true>(k.res[adds], off[j]);
@@ -72,7 +74,7 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
             }
             // from here on the residual's gradient collects the same factors as the input's
 #pragma unroll
-            for (int n = 0; n < K_MAX_RES; ++n)
+            for (int n = 0; n < NR; ++n)
                 if (n == adds) {
 #pragma unroll
                     for (int j = 0; j < R; ++j)
@@ -157,16 +159,16 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
             for (int e = 0; e < VEC; ++e) {
                 t[j][e] *= f[j][e];
 #pragma unroll
-                for (int n = 0; n < K_MAX_RES; ++n) r[n][j][e] *= f[j][e];
+                for (int n = 0; n < NR; ++n) r[n][j][e] *= f[j][e];
             }
     }
     return adds;
 }
 
 // Write grad_in = s * t and grad_residual[n] = s * r[n] for one register row.
-template <int DT, int VEC, int R>
+template <int DT, int VEC, int R, int NR = K_MAX_RES>
 BS_DEV void store_row(const BwdK &k, int j, uint32_t off, int32_t adds, const float (&s)[VEC], const float (&t)[R][VEC],
-                      const float (&r)[K_MAX_RES][R][VEC])
+                      const float (&r)[NR ? NR : 1][R][VEC])
 {
     if (k.g_in) {
         float v[VEC];
@@ -175,7 +177,7 @@ BS_DEV void store_row(const BwdK &k, int j, uint32_t off, int32_t adds, const fl
         store_elems<DT, VEC>(k.g_in, off, v);
     }
 #pragma unroll
-    for (int n = 0; n < K_MAX_RES; ++n)
+    for (int n = 0; n < NR; ++n)
         if (n < adds && k.g_res[n]) {
             float v[VEC];
 #pragma unroll
@@ -344,7 +346,7 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
 // order, as the forward kernels do) and writes the gradients of all its cells.  No recorded
 // picks, no recomputation pass: the stage input and the gradient with respect to it move once.
 // =============================================================================
-template <int DT, int VEC>
+template <int DT, int VEC, int NR>
 __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 {
     constexpr int NO = VEC / 2;
@@ -364,12 +366,12 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 
     const Raw<DT, VEC> a0 = load_raw<DT, VEC, true>(k.a, offs[0]), a1 = load_raw<DT, VEC, true>(k.a, offs[1]);
     const Raw<DT, NO> gr = load_raw<DT, NO, true>(k.g_out, out_off);
-    float x[2][VEC], t[2][VEC], r[K_MAX_RES][2][VEC], g[NO];
+    float x[2][VEC], t[2][VEC], r[NR ? NR : 1][2][VEC], g[NO];
     unpack<DT, VEC>(a0, x[0]);
     unpack<DT, VEC>(a1, x[1]);
     unpack<DT, NO>(gr, g);
     const int32_t cs[2] = {c, c};
-    const int32_t adds = ew_sweep<DT, VEC, 2>(k, cs, offs, x, t, r);
+    const int32_t adds = ew_sweep<DT, VEC, 2, false, NR>(k, cs, offs, x, t, r);
 
     float s[2][VEC];
     if (k.pool.kind == OP_MAXPOOL) {
@@ -401,8 +403,8 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
         }
     }
     if (!live) return;
-    store_row<DT, VEC, 2>(k, 0, offs[0], adds, s[0], t, r);
-    store_row<DT, VEC, 2>(k, 1, offs[1], adds, s[1], t, r);
+    store_row<DT, VEC, 2, NR>(k, 0, offs[0], adds, s[0], t, r);
+    store_row<DT, VEC, 2, NR>(k, 1, offs[1], adds, s[1], t, r);
 }
 
 // =============================================================================
@@ -484,7 +486,7 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
 
 // Disjoint 2 x 2 windows that tile the plane, channels-last: a lane owns VEC channels of one
 // window's four pixels (row-major window order: the order of the first-maximum rule).
-template <int DT, int VEC>
+template <int DT, int VEC, int NR>
 __global__ __launch_bounds__(256) void bwd_direct2_nhwc_kernel(const BwdK k)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -508,12 +510,12 @@ __global__ __launch_bounds__(256) void bwd_direct2_nhwc_kernel(const BwdK k)
 #pragma unroll
     for (int j = 0; j < 4; ++j) raw[j] = load_raw<DT, VEC, true>(k.a, offs[j]);
     const Raw<DT, VEC> gr = load_raw<DT, VEC, true>(k.g_out, out_off);
-    float x[4][VEC], t[4][VEC], r[K_MAX_RES][4][VEC], g[VEC];
+    float x[4][VEC], t[4][VEC], r[NR ? NR : 1][4][VEC], g[VEC];
 #pragma unroll
     for (int j = 0; j < 4; ++j) unpack<DT, VEC>(raw[j], x[j]);
     unpack<DT, VEC>(gr, g);
     const int32_t cs[4] = {c0, c0, c0, c0};
-    const int32_t adds = ew_sweep<DT, VEC, 4, true>(k, cs, offs, x, t, r);
+    const int32_t adds = ew_sweep<DT, VEC, 4, true, NR>(k, cs, offs, x, t, r);
 
     float s[4][VEC];
     if (k.pool.kind == OP_MAXPOOL) {
@@ -540,7 +542,7 @@ __global__ __launch_bounds__(256) void bwd_direct2_nhwc_kernel(const BwdK k)
     }
     if (!live) return;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) store_row<DT, VEC, 4>(k, j, offs[j], adds, s[j], t, r);
+    for (int j = 0; j < 4; ++j) store_row<DT, VEC, 4, NR>(k, j, offs[j], adds, s[j], t, r);
 }
 
 static void set_error(hipError_t e) { set_hip_error((int32_t)e); }
@@ -567,6 +569,9 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     if (grid < 1 || grid > 0x7fffffffll || threads != 256) return BS_ERR_UNSUPPORTED;
     if (k.n_ew < 0 || k.n_ew > K_BWD_EW) return BS_ERR_UNSUPPORTED;
     const dim3 g((uint32_t)grid), b((uint32_t)threads);
+    // a stage without Add gets the instances that keep no residual gradients in registers
+    bool has_add = false;
+    for (int32_t j = 0; j < k.n_ew; ++j) has_add = has_add || k.ew[j].kind == OP_ADD;
     if (k.nhwc) {
         // a lane per (pixel or window, channel vector): the divisors must be the ones the kernels assume
         if ((vec != 1 && vec != full) || k.C % vec != 0 || (int64_t)k.div_wv.d * vec != k.C ||
@@ -580,7 +585,8 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         if (!k.direct && p.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
 #define BS_LAUNCH_NHWC(DT, V)                                                          \
     do {                                                                               \
-        if (k.direct) bwd_direct2_nhwc_kernel<DT, V><<<g, b, 0, st>>>(k);              \
+        if (k.direct && !has_add) bwd_direct2_nhwc_kernel<DT, V, 0><<<g, b, 0, st>>>(k); \
+        else if (k.direct) bwd_direct2_nhwc_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k); \
         else bwd_stage_nhwc_kernel<DT, V><<<g, b, 0, st>>>(k);                         \
     } while (0)
         if (dtype == BS_F32) { if (vec == 4) BS_LAUNCH_NHWC(DT_F32, 4); else BS_LAUNCH_NHWC(DT_F32, 1); }
@@ -604,10 +610,18 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         if ((p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 2 || p.kw != 2 || p.sh != 2 || p.sw != 2 || p.ph != 0 ||
             p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo || vec != full)
             return BS_ERR_UNSUPPORTED;
-        if (dtype == BS_F32) bwd_direct2_kernel<DT_F32, 4><<<g, b, 0, st>>>(k);
-        else if (dtype == BS_BF16) bwd_direct2_kernel<DT_BF16, 8><<<g, b, 0, st>>>(k);
-        else if (dtype == BS_F16) bwd_direct2_kernel<DT_F16, 8><<<g, b, 0, st>>>(k);
-        else return BS_ERR_UNSUPPORTED;
+        if (dtype == BS_F32) {
+            if (has_add) bwd_direct2_kernel<DT_F32, 4, K_MAX_RES><<<g, b, 0, st>>>(k);
+            else bwd_direct2_kernel<DT_F32, 4, 0><<<g, b, 0, st>>>(k);
+        } else if (dtype == BS_BF16) {
+            if (has_add) bwd_direct2_kernel<DT_BF16, 8, K_MAX_RES><<<g, b, 0, st>>>(k);
+            else bwd_direct2_kernel<DT_BF16, 8, 0><<<g, b, 0, st>>>(k);
+        } else if (dtype == BS_F16) {
+            if (has_add) bwd_direct2_kernel<DT_F16, 8, K_MAX_RES><<<g, b, 0, st>>>(k);
+            else bwd_direct2_kernel<DT_F16, 8, 0><<<g, b, 0, st>>>(k);
+        } else {
+            return BS_ERR_UNSUPPORTED;
+        }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error(e);
