@@ -44,9 +44,11 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // CL: channels-last -- the VEC cells of a row are consecutive channels c[j] .. c[j] + VEC - 1 of one
 // pixel (all rows hold the same channels), so BatchNorm parameters are per-cell vectors.
 // NR: residual gradients kept (K_MAX_RES, or 0 for a stage without Add: no registers for them).
+// nfirst (row-major only): cells of row j that lie in channel c[j]; the rest lie in the next channel
+// (a vector that straddles two planes).  Null: every cell of row j lies in channel c[j].
 template <int DT, int VEC, int R, bool CL = false, int NR = K_MAX_RES>
 BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
-                        float (&r)[NR ? NR : 1][R][VEC])
+                        float (&r)[NR ? NR : 1][R][VEC], const uint32_t *nfirst = nullptr)
 {
 #pragma unroll
     for (int j = 0; j < R; ++j)
@@ -112,18 +114,27 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
                         x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc[e], sh[e]));
                     }
             } else {
-                float sc[R], sh[R];
+                float sc[R], sh[R], sc1[R], sh1[R];
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
                     sc[j] = k.params[arg + c[j]];
                     sh[j] = k.params[arg + k.C + c[j]];
+                    if (nfirst) {
+                        const int32_t cn = c[j] + 1 == k.C ? 0 : c[j] + 1;
+                        sc1[j] = k.params[arg + cn];
+                        sh1[j] = k.params[arg + k.C + cn];
+                    } else {
+                        sc1[j] = sc[j];
+                        sh1[j] = sh[j];
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < R; ++j)
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
-                        f[j][e] = sc[j];
-                        x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], sc[j], sh[j]));
+                        const bool first = !nfirst || (uint32_t)e < nfirst[j];
+                        f[j][e] = first ? sc[j] : sc1[j];
+                        x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], f[j][e], first ? sh[j] : sh1[j]));
                     }
             }
         } else if (kind == OP_RELU) {
@@ -310,7 +321,7 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
     const uint32_t nvec = k.total;                      // vectors in the tensor
     bool live[U];
-    uint32_t offs[U];
+    uint32_t offs[U], nfirst[U];
     int32_t cs[U];
     Raw<DT, VEC> ar[U], gr[U];
 #pragma unroll
@@ -319,8 +330,16 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
         live[u] = i < nvec;
         i = live[u] ? i : 0u;
         offs[u] = i * VEC;
-        // plane = i / hwv by way of the row: i / (W / VEC) / H
-        const uint32_t plane = fdiv(fdiv(i, k.div_wv), k.div_h);
+        uint32_t plane;
+        if (k.flat) {
+            // vectors over the whole tensor: this one begins in `plane` and may end in the next one
+            // (never further: a plane has at least VEC cells)
+            plane = fdiv(offs[u], k.div_w);
+            nfirst[u] = k.div_w.d - (offs[u] - plane * k.div_w.d);
+        } else {
+            plane = fdiv(fdiv(i, k.div_wv), k.div_h);  // i / (W / VEC) / H
+            nfirst[u] = VEC;
+        }
         cs[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
         ar[u] = load_raw<DT, VEC, true>(k.a, offs[u]);
         gr[u] = load_raw<DT, VEC, true>(k.g_out, offs[u]);
@@ -331,7 +350,7 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
         unpack<DT, VEC>(ar[u], x[u]);
         unpack<DT, VEC>(gr[u], s[u]);
     }
-    const int32_t adds = ew_sweep<DT, VEC, U>(k, cs, offs, x, t, r);
+    const int32_t adds = ew_sweep<DT, VEC, U>(k, cs, offs, x, t, r, k.flat ? nfirst : nullptr);
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (live[u]) store_row<DT, VEC, U>(k, u, offs[u], adds, s[u], t, r);
@@ -601,9 +620,16 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         }
         return BS_OK;
     }
-    if ((vec != 1 && vec != full) || k.W % vec != 0 || (int64_t)k.div_wv.d * vec != k.W ||
-        (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_c.d != k.C || (int64_t)grid * threads < (int64_t)k.total)
+    if (k.flat) {
+        // vectors that run over plane boundaries: no pooling, whole vectors, a plane of at least one vector
+        if (k.pool.kind != 0 || vec != full || (int64_t)k.div_w.d != (int64_t)k.H * k.W || (int64_t)k.H * k.W < vec ||
+            (int64_t)k.div_c.d != k.C || (int64_t)grid * threads < (int64_t)k.total)
+            return BS_ERR_UNSUPPORTED;
+    } else if ((vec != 1 && vec != full) || k.W % vec != 0 || (int64_t)k.div_wv.d * vec != k.W ||
+               (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_c.d != k.C ||
+               (int64_t)grid * threads < (int64_t)k.total) {
         return BS_ERR_UNSUPPORTED;
+    }
     if (k.direct) {
         const PoolK &p = k.pool;
         // what the kernel assumes: 2 x 2 windows, stride 2, no padding, tiling the plane; whole vectors

@@ -226,6 +226,9 @@ struct BwdK {
                           // of one window's four pixels); total = pixels (direct: windows) * (C / vec), div_wv
                           // divides by C / vec, div_h by H (direct: Ho), div_w by W (direct: Wo)
     FastDiv div_w;
+    int32_t flat;         // 1 (row-major, no pooling): planes are no whole number of vectors; the tensor is one run of
+                          // `vec`-element vectors that may begin in one plane and end in the next; total = vectors,
+                          // div_w divides by H * W
 };
 
 #if defined(__HIPCC__)

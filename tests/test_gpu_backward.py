@@ -159,6 +159,18 @@ def test_channels_last_disjoint_two_by_two_windows(dtype):
     _close(got, ref, dtype, "channels-last ties")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_planes_that_are_no_whole_number_of_vectors(dtype):
+    """Element-wise stages on 14 x 14 and 7 x 7 planes: vectors run over the whole tensor and may begin in
+    one plane (channel, image) and end in the next."""
+    for c, shape in ((5, (2, 5, 14, 14)), (8, (3, 8, 7, 7)), (3, (8, 3, 3, 3))):
+        layers = [wl.bn_params(c, 1), wl.add(), wl.leaky_relu(0.2), wl.bn_params(c, 2), wl.add(), wl.relu()]
+        check(layers, shape, dtype, f"vectors over plane boundaries {shape}")
+    # behind a pooling stage as well (the element-wise stage after the pool is the flat one)
+    layers = [wl.bn_params(6, 3), wl.relu(), wl.maxpool(2, 2), wl.bn_params(6, 4), wl.add(), wl.relu()]
+    check(layers, (4, 6, 28, 28), dtype, "flat stage behind a pooling stage")
+
+
 def test_long_lists_are_cut_into_stages():
     c = 4
     # 20 element-wise operations (more than one argument block holds), 6 Adds (more than one stage's residual slots)
