@@ -342,7 +342,9 @@ BS_API bs_status bs_stack_check_buffers(const bs_stack *stack, const void *in, i
  * then in that layout, dense).  BatchNorm is the inference-mode layer (constant folded
  * parameters): gradients are produced for the stack's input and its residual operands, none
  * for BatchNorm parameters.
- * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED (no device plan), BS_ERR_UNSUPPORTED (a tensor of 2^31
+ * After a host-only plan it builds the stages, their (host-only) forward plans and the workspace size, which
+ * bs_stack_backward_num_stages / _workspace_bytes report; bs_stack_backward then returns BS_ERR_NOT_PLANNED.
+ * Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED (no plan), BS_ERR_UNSUPPORTED (a tensor of 2^31
  *         lanes), BS_ERR_DEVICE, BS_ERR_ALLOC, and those of bs_stack_plan for the stage plans.
  */
 BS_API bs_status bs_stack_plan_backward(bs_stack *stack);

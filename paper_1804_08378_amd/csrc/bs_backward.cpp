@@ -36,7 +36,7 @@ inline bool overlap(const void *a, uint64_t na, const void *b, uint64_t nb)
 }
 
 // The stage's layers as a forward stack of their own, planned with the stack's options.
-bs_status make_forward(const bs_stack *s, BwdStage &g)
+bs_status make_forward(const bs_stack *s, BwdStage &g, bool host_only)
 {
     std::vector<bs_layer_desc> descs((size_t)g.n_layers);
     for (int32_t i = 0; i < g.n_layers; ++i) {
@@ -58,7 +58,7 @@ bs_status make_forward(const bs_stack *s, BwdStage &g)
         return BS_ERR_SHAPE;
     }
     bs_plan_options o = s->opts;
-    o.host_only = 0;
+    o.host_only = host_only ? 1 : 0;
     o.breadth_first = 0;
     o.force_variant = BS_VARIANT_AUTO;
     st = bs_stack_plan(f, &o);
@@ -87,8 +87,10 @@ void free_backward(bs_stack *s)
 extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
 {
     if (!stack) return BS_ERR_NULL;
-    if (!stack->planned || !stack->device_planned) return BS_ERR_NOT_PLANNED;
-    if (current_device() != stack->device) return BS_ERR_DEVICE;
+    if (!stack->planned) return BS_ERR_NOT_PLANNED;
+    // on a host-only plan: stages, stage plans and workspace size, nothing that can run
+    const bool host_only = !stack->device_planned;
+    if (!host_only && current_device() != stack->device) return BS_ERR_DEVICE;
     free_backward(stack);
     BackwardPlan *plan = new (std::nothrow) BackwardPlan();
     if (!plan) return BS_ERR_ALLOC;
@@ -195,7 +197,7 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
             // the buffers are sized by these shapes: a stage must end where the next one begins
             const int64_t *next = j + 1 < S ? plan->stages[j + 1].in_shape : stack->out_shape;
             if (std::memcmp(g.out_shape, next, sizeof g.out_shape) != 0) { st = BS_ERR_SHAPE; break; }
-            if (j + 1 < S || is_max) st = make_forward(stack, g);
+            if (j + 1 < S || is_max) st = make_forward(stack, g, host_only);
             if (st != BS_OK) break;
             if (j > 0) {
                 g.a_off = off;

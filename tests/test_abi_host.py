@@ -144,12 +144,60 @@ def test_backward_entry_points_without_a_device_plan():
         assert bs.bs_stack_backward_num_stages(h) == -1 and bs.bs_stack_backward_workspace_bytes(h) == 0
         assert _status(bs.bs_stack_plan_backward, h) == 5           # not planned at all
         bs.bs_stack_plan(h, host_only=1)
-        assert _status(bs.bs_stack_plan_backward, h) == 5           # host-only plan
         assert _status(bs.bs_stack_backward, h, 16, None, 32, 48, None, 0, 0, 0) == 5
+        bs.bs_stack_plan_backward(h)                                # host-only: stages and sizes, nothing that runs
+        assert bs.bs_stack_backward_num_stages(h) == 1
+        assert _status(bs.bs_stack_backward, h, 16, None, 32, 48, None, 0, 0, 0) == 5
+        bs.bs_stack_plan(h, host_only=1)                            # a new plan drops the backward plan
         assert bs.bs_stack_backward_num_stages(h) == -1
         assert _status(bs.bs_stack_plan_backward, None) == 1
     finally:
         bs.bs_stack_destroy(h)
+
+
+def _backward_plan(layers, shape, dtype="f32", **opts):
+    h = bs.bs_stack_create(layers, shape, dtype)
+    try:
+        bs.bs_stack_plan(h, host_only=1, **opts)
+        bs.bs_stack_plan_backward(h)
+        return bs.bs_stack_backward_num_stages(h), bs.bs_stack_backward_workspace_bytes(h)
+    finally:
+        bs.bs_stack_destroy(h)
+
+
+def test_backward_stages_and_workspace():
+    """A stage is a run of element-wise operations with at most one pooling operation at its end.  The
+    workspace holds, 256-byte aligned: input and input gradient of every stage after the first, the picks
+    of every max pooling that does not find them itself, the unused output of a last stage that is run
+    forward for its picks, and the forward stage plans' own workspace."""
+    c, shape = 8, (2, 8, 16, 16)
+    al = lambda n: (n + 255) // 256 * 256
+    bn = lambda i: wl.bn_params(c, i)
+    # one stage, nothing to recompute
+    assert _backward_plan([bn(0), wl.add(), wl.relu()], shape) == (1, 0)
+    assert _backward_plan([bn(0), wl.relu(), wl.avgpool(3, 2, 1)], shape) == (1, 0)
+    # 2 x 2 windows that tile the plane find their picks themselves, in both layouts
+    assert _backward_plan([bn(0), wl.relu(), wl.maxpool(2, 2)], shape) == (1, 0)
+    assert _backward_plan([bn(0), wl.relu(), wl.maxpool(2, 2)], shape, layout=bs.BS_LAYOUT_NHWC) == (1, 0)
+    # ... unless the rows are no whole vectors (float32: 4 per vector) or the plane is odd
+    n_out = 2 * 8 * 7 * 7
+    assert _backward_plan([bn(0), wl.relu(), wl.maxpool(2, 2)], (2, 8, 14, 14)) == (1, al(n_out * 4) + al(n_out * 4))
+    # overlapping windows: picks (int32) and the forward run's output
+    n_out = 2 * 8 * 8 * 8
+    assert _backward_plan([bn(0), wl.relu(), wl.maxpool(3, 2, 1)], shape) == (1, al(n_out * 4) + al(n_out * 4))
+    assert _backward_plan([bn(0), wl.relu(), wl.maxpool(3, 2, 1)], shape, "f16") == (1, al(n_out * 4) + al(n_out * 2))
+    # pool, then element-wise operations: two stages; the second one's input and input gradient
+    stages, ws = _backward_plan([bn(0), wl.relu(), wl.avgpool(2, 2), bn(1), wl.relu()], shape)
+    assert (stages, ws) == (2, 2 * al(n_out * 4))
+    # three stages (the halo stress stack): stage 1 = max pooling alone, stage 2 = BatchNorm, ReLU
+    n_in = 2 * 8 * 16 * 16
+    stages, ws = _backward_plan([bn(0), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1), bn(1), wl.relu()], shape)
+    assert stages == 3 and ws >= 2 * al(n_in * 4) + al(n_out * 4) + 2 * al(n_out * 4)
+    # capacity: 16 element-wise operations and 4 residual operands per stage
+    assert _backward_plan([wl.relu()] * 16, shape)[0] == 1
+    assert _backward_plan([wl.relu()] * 17, shape)[0] == 2
+    assert _backward_plan([wl.add()] * 4, shape)[0] == 1
+    assert _backward_plan([wl.add()] * 5, shape)[0] == 2
 
 
 def test_size_limit_is_two_to_the_31_elements():
