@@ -1,6 +1,6 @@
 // Host-side robustness driver: random layer lists (valid and invalid) through
-// bs_stack_create, host-only bs_stack_plan with random options, every query, the error
-// paths of bs_stack_run, and bs_stack_destroy.  Built with AddressSanitizer and
+// bs_stack_create, host-only bs_stack_plan with random options, every query, the backward
+// plan on top of it, the error paths of bs_stack_run / bs_stack_backward, and bs_stack_destroy.  Built with AddressSanitizer and
 // UndefinedBehaviorSanitizer against a host-only build of the library (tests/test_host_sanitize.py);
 // touches no device.
 #include <cstdint>
@@ -20,7 +20,7 @@ static uint32_t rnd(uint32_t n)
 int main(int argc, char **argv)
 {
     const int cases = argc > 1 ? std::atoi(argv[1]) : 2000;
-    int created = 0, planned = 0, declined = 0;
+    int created = 0, planned = 0, declined = 0, backward_plans = 0;
     for (int it = 0; it < cases; ++it) {
         const int64_t shape[4] = {1 + rnd(3), 1 + rnd(6), 1 + rnd(48), 1 + rnd(48)};
         const int64_t C = shape[1];
@@ -95,6 +95,20 @@ int main(int argc, char **argv)
             for (int32_t t = -1; t <= pi.n_steps; ++t) { bs_step_info ti{}; (void)bs_stack_step_info(s, t, &ti); }
             for (int32_t t = -1; t <= pi.n_operations; ++t) (void)bs_stack_operation_name(s, t);
             (void)bs_stack_workspace_bytes(s);
+            // backward plan on the host-only plan: stages and their forward plans are built and freed
+            if (rnd(2) == 0) {
+                const bs_status bp = bs_stack_plan_backward(s);
+                const int32_t stages = bs_stack_backward_num_stages(s);
+                if ((bp == BS_OK) != (stages >= 1)) { std::puts("backward plan and stage count disagree"); return 1; }
+                if (bp == BS_OK && stages > pi.n_operations + 1) { std::puts("more stages than operations"); return 1; }
+                (void)bs_stack_backward_workspace_bytes(s);
+                float dummy[4] = {0, 0, 0, 0};
+                if (bs_stack_backward(s, dummy, nullptr, dummy, dummy, nullptr, nullptr, 0, nullptr) == BS_OK) {
+                    std::puts("backward succeeded on a host-only plan");
+                    return 1;
+                }
+                ++backward_plans;
+            }
             if (pi.device_planned == 0) {
                 float dummy[4] = {0, 0, 0, 0};
                 if (bs_stack_run(s, dummy, nullptr, dummy, nullptr, nullptr, 0, nullptr) == BS_OK) {
@@ -106,6 +120,6 @@ int main(int argc, char **argv)
         bs_stack_destroy(s);
     }
     bs_stack_destroy(nullptr);
-    std::printf("ok: %d created, %d declined at create, %d plans\n", created, declined, planned);
+    std::printf("ok: %d created, %d declined at create, %d plans, %d backward plans\n", created, declined, planned, backward_plans);
     return 0;
 }
