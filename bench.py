@@ -456,7 +456,7 @@ def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30, channels_la
 
             def ours():
                 i = cur[0] = (cur[0] + 1) % sets
-                bs.bs_stack_backward(st.handle, xs[i].data_ptr(), [r.data_ptr() for r in rs[i]], dys[i].data_ptr(),
+                bs.bs_stack_backward(st.handle, xs[i].data_ptr(), [r.data_ptr() for r in rs[i]], None, dys[i].data_ptr(),
                                      gx[i].data_ptr(), [t.data_ptr() for t in gr[i]], ws.data_ptr(), wsn, stream)
 
             outs = [st.alloc_outputs("cuda", False)[0] for _ in range(sets)]
@@ -464,11 +464,27 @@ def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30, channels_la
             def ours_fb():
                 i = cur[0] = (cur[0] + 1) % sets
                 st.run(xs[i], rs[i], out=outs[i], indices=[])
-                bs.bs_stack_backward(st.handle, xs[i].data_ptr(), [r.data_ptr() for r in rs[i]], dys[i].data_ptr(),
+                bs.bs_stack_backward(st.handle, xs[i].data_ptr(), [r.data_ptr() for r in rs[i]], None, dys[i].data_ptr(),
                                      gx[i].data_ptr(), [t.data_ptr() for t in gr[i]], ws.data_ptr(), wsn, stream)
 
             ms, mn = timed(ours, steps)
             ms_fb, _ = timed(ours_fb, steps)
+            # with the picks kept from the forward pass (index outputs of bs_stack_run) instead of recomputed
+            ms_kept = None
+            layers_idx = wl.build(name, 0, None, True)[0]
+            if any(l.get("return_indices") for l in layers_idx):
+                st2 = bs.Stack(layers_idx, shape, dt).plan(layout=1 if channels_last else 0).plan_backward()
+                kept = [st2.run(xs[i], rs[i])[1] for i in range(sets)]
+
+                def ours_kept():
+                    i = cur[0] = (cur[0] + 1) % sets
+                    bs.bs_stack_backward(st2.handle, xs[i].data_ptr(), [r.data_ptr() for r in rs[i]], [t.data_ptr() for t in kept[i]],
+                                         dys[i].data_ptr(), gx[i].data_ptr(), [t.data_ptr() for t in gr[i]], ws.data_ptr(), wsn, stream)
+
+                if bs.bs_stack_backward_workspace_bytes(st2.handle) <= max(wsn, 16):
+                    ms_kept, _ = timed(ours_kept, steps)
+                st2.close()
+                del kept
             # the framework: parameters on the device, one retained graph per buffer set
             tl = []
             for l in layers:
@@ -501,12 +517,13 @@ def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30, channels_la
             row = {"config": name, "dtype": dt, "stages": stages, "MB": nbytes / 1e6, "us_mean": ms * 1e3, "us_min": mn * 1e3,
                    "GBps": gbps, "pct_peak": 100 * gbps / HBM_PEAK_GBPS, "autograd_backward_us": ms_t * 1e3,
                    "speedup_backward": ms_t / ms, "forward_backward_us": ms_fb * 1e3,
-                   "autograd_forward_backward_us": ms_tfb * 1e3, "speedup_forward_backward": ms_tfb / ms_fb}
+                   "autograd_forward_backward_us": ms_tfb * 1e3, "speedup_forward_backward": ms_tfb / ms_fb,
+                   "us_mean_with_saved_picks": None if ms_kept is None else ms_kept * 1e3}
             rows.append(row)
             log(f"{name:<16}{dt:<6}{stages:>7}{row['MB']:>8.1f}{row['us_mean']:>9.1f}{row['us_min']:>8.1f}{gbps:>8.0f}"
                 f"{row['pct_peak']:>7.1f}{row['autograd_backward_us']:>12.1f}{row['speedup_backward']:>8.2f}"
                 f"{row['forward_backward_us']:>9.1f}{row['autograd_forward_backward_us']:>10.1f}"
-                f"{row['speedup_forward_backward']:>8.2f}")
+                f"{row['speedup_forward_backward']:>8.2f}" + ("" if ms_kept is None else f"   with saved picks {ms_kept * 1e3:.1f} us"))
             st.close()
             del xs, rs, dys, gx, gr, outs, ws
             torch.cuda.empty_cache()

@@ -364,6 +364,12 @@ BS_API int32_t bs_stack_backward_num_stages(const bs_stack *stack);
  * lo <= input <= hi; average pooling uses the forward pass's divisor per window; overlapping
  * windows add up.  Arithmetic is float32, each result rounded once to the stack dtype.
  *   in, residuals    device, as in bs_stack_run (dense, the forward pass's values)
+ *   indices          host array of bs_stack_num_index_outputs() DEVICE int32 pointers: index outputs
+ *                    that bs_stack_run wrote for this `in` (the saved picks of max-pooling layers
+ *                    created with return_indices); the array or single entries may be NULL.  Where
+ *                    given for the stack's last pooling layer, the forward run that would recompute
+ *                    them is skipped; they are trusted (a cell index outside its window or plane
+ *                    only misroutes that gradient, it is never used as an address)
  *   grad_out         device, dense, bs_stack_output_shape() elements of the stack dtype
  *   grad_in          device, dense, the input's shape and dtype; NULL = not wanted
  *   grad_residuals   host array of bs_stack_num_residuals() DEVICE pointers (shapes of the
@@ -375,8 +381,9 @@ BS_API int32_t bs_stack_backward_num_stages(const bs_stack *stack);
  *         BS_ERR_WORKSPACE, BS_ERR_ALIAS, BS_ERR_HIP.
  */
 BS_API bs_status bs_stack_backward(const bs_stack *stack, const void *in, const void *const *residuals,
-                                   const void *grad_out, void *grad_in, void *const *grad_residuals,
-                                   void *workspace, uint64_t workspace_bytes, void *stream);
+                                   const int32_t *const *indices, const void *grad_out, void *grad_in,
+                                   void *const *grad_residuals, void *workspace, uint64_t workspace_bytes,
+                                   void *stream);
 
 /*
  * Compile, without loading them and without touching any device, all run-time builds the

@@ -105,8 +105,8 @@ _SIGNATURES = {
     "bs_stack_plan_backward": (C.c_int, [C.c_void_p]),
     "bs_stack_backward_workspace_bytes": (C.c_uint64, [C.c_void_p]),
     "bs_stack_backward_num_stages": (C.c_int32, [C.c_void_p]),
-    "bs_stack_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
-                                    C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_stack_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p,
+                                    C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
     "bs_stack_jit_check": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]),
     "bs_jit_log": (C.c_char_p, []),
     "bs_status_string": (C.c_char_p, [C.c_int]),
@@ -344,17 +344,21 @@ def bs_stack_backward_num_stages(handle) -> int:
     return int(load().bs_stack_backward_num_stages(C.c_void_p(handle)))
 
 
-def bs_stack_backward(handle, in_ptr, residual_ptrs, grad_out_ptr, grad_in_ptr, grad_residual_ptrs, workspace_ptr,
-                      workspace_bytes, stream) -> None:
-    """All *_ptr arguments are integer device addresses (0 / None = NULL: that gradient is not wanted)."""
-    res = gres = None
+def bs_stack_backward(handle, in_ptr, residual_ptrs, index_ptrs, grad_out_ptr, grad_in_ptr, grad_residual_ptrs,
+                      workspace_ptr, workspace_bytes, stream) -> None:
+    """All *_ptr arguments are integer device addresses (0 / None = NULL: that gradient is not wanted, those
+    saved indices are not there)."""
+    res = gres = idx = None
     if residual_ptrs:
         res = (C.c_void_p * len(residual_ptrs))(*[C.c_void_p(p or None) for p in residual_ptrs])
+    if index_ptrs:
+        idx = (C.c_void_p * len(index_ptrs))(*[C.c_void_p(p or None) for p in index_ptrs])
     if grad_residual_ptrs:
         gres = (C.c_void_p * len(grad_residual_ptrs))(*[C.c_void_p(p or None) for p in grad_residual_ptrs])
-    _check(load().bs_stack_backward(C.c_void_p(handle), C.c_void_p(in_ptr or None), res, C.c_void_p(grad_out_ptr or None),
-                                    C.c_void_p(grad_in_ptr or None), gres, C.c_void_p(workspace_ptr or None),
-                                    int(workspace_bytes), C.c_void_p(stream or None)), "bs_stack_backward")
+    _check(load().bs_stack_backward(C.c_void_p(handle), C.c_void_p(in_ptr or None), res, idx,
+                                    C.c_void_p(grad_out_ptr or None), C.c_void_p(grad_in_ptr or None), gres,
+                                    C.c_void_p(workspace_ptr or None), int(workspace_bytes), C.c_void_p(stream or None)),
+           "bs_stack_backward")
 
 
 def bs_stack_run_strided(handle, in_ptr, in_batch_stride, residual_ptrs, out_ptr, out_batch_stride,
@@ -453,8 +457,10 @@ class Stack:
         self._bwd_workspace = None
         return self
 
-    def backward(self, x, residuals, grad_out, need_input_grad=True, need_residual_grads=None, stream=None):
+    def backward(self, x, residuals, grad_out, need_input_grad=True, need_residual_grads=None, stream=None, indices=None):
         """Enqueue the backward pass; returns (grad_x or None, [grad_residual or None, ...]).
+        `indices`: the index outputs `run` wrote for this `x` (entries may be None), which save
+        recomputing the last pooling layer's picks.
         `x` and `residuals` are the forward pass's operands, `grad_out` the gradient with respect
         to its output; all dense tensors of the stack's dtype in the plan's memory layout (the
         gradients come back in that layout)."""
@@ -480,7 +486,15 @@ class Stack:
             self._bwd_workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
         ws = self._bwd_workspace if n else None
         st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
-        bs_stack_backward(self.handle, x.data_ptr(), [r.data_ptr() for r in residuals], grad_out.data_ptr(),
+        if indices is not None:
+            if len(indices) != self.n_idx:
+                raise ValueError(f"the stack has {self.n_idx} index outputs")
+            for i, t in enumerate(indices):
+                if t is not None and (tuple(t.shape) != bs_stack_index_shape(self.handle, i) or t.dtype != torch.int32 or
+                                      not t.is_contiguous(memory_format=mf)):
+                    raise ValueError("saved indices must be the int32 index outputs of run()")
+        idx = [t.data_ptr() if t is not None else 0 for t in indices] if indices else None
+        bs_stack_backward(self.handle, x.data_ptr(), [r.data_ptr() for r in residuals], idx, grad_out.data_ptr(),
                           gx.data_ptr() if gx is not None else 0, [g.data_ptr() if g is not None else 0 for g in gres],
                           ws.data_ptr() if ws is not None else 0, n, st)
         return gx, gres

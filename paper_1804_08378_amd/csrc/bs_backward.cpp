@@ -143,6 +143,7 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
             p.count_include_pad = op.count_include_pad;
             p.inv_kk = 1.0f / (float)(op.kh * op.kw);
             p.idx_slot = -1;
+            cur.idx_slot = op.kind == OP_MAXPOOL ? op.idx_slot : -1;
             cur.k.Ho = op.out_h;
             cur.k.Wo = op.out_w;
             cur.out_shape[2] = op.out_h;
@@ -238,8 +239,9 @@ extern "C" int32_t bs_stack_backward_num_stages(const bs_stack *stack)
 }
 
 extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, const void *const *residuals,
-                                       const void *grad_out, void *grad_in, void *const *grad_residuals,
-                                       void *workspace, uint64_t workspace_bytes, void *stream)
+                                       const int32_t *const *indices, const void *grad_out, void *grad_in,
+                                       void *const *grad_residuals, void *workspace, uint64_t workspace_bytes,
+                                       void *stream)
 {
     if (!stack || !in || !grad_out) return BS_ERR_NULL;
     if (!stack->planned || !stack->device_planned || !stack->backward) return BS_ERR_NOT_PLANNED;
@@ -264,22 +266,36 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         if (!workspace || workspace_bytes < plan.workspace_bytes) return BS_ERR_WORKSPACE;
         ins[n_in++] = Buf{workspace, plan.workspace_bytes};
     }
+    Buf saved[BS_MAX_INDEX_OUTPUTS];
+    int n_saved = 0;
+    for (int32_t i = 0; i < stack->n_idx; ++i)
+        if (indices && indices[i]) saved[n_saved++] = Buf{indices[i], numel(stack->idx_shape[i]) * 4};
+    for (int i = 0; i < n_saved; ++i)
+        if (!aligned16(saved[i].p)) return BS_ERR_ALIGN;
     for (int i = 0; i < n_in; ++i)
         if (!aligned16(ins[i].p)) return BS_ERR_ALIGN;
     for (int i = 0; i < n_out; ++i) {
         if (!aligned16(outs[i].p)) return BS_ERR_ALIGN;
         for (int j = 0; j < n_in; ++j)
             if (overlap(outs[i].p, outs[i].bytes, ins[j].p, ins[j].bytes)) return BS_ERR_ALIAS;
+        for (int j = 0; j < n_saved; ++j)
+            if (overlap(outs[i].p, outs[i].bytes, saved[j].p, saved[j].bytes)) return BS_ERR_ALIAS;
         for (int j = 0; j < i; ++j)
             if (overlap(outs[i].p, outs[i].bytes, outs[j].p, outs[j].bytes)) return BS_ERR_ALIAS;
     }
 
     char *ws = static_cast<char *>(workspace);
     const size_t S = plan.stages.size();
+    // picks the caller kept from the forward pass (index outputs of bs_stack_run), per stage
+    auto kept = [&](const BwdStage &g) -> const int32_t * {
+        return indices && g.idx_slot >= 0 ? indices[g.idx_slot] : nullptr;
+    };
     // ---- recompute: the input of every stage after the first, the picks of every max pooling
     for (size_t j = 0; j < S; ++j) {
         const BwdStage &g = plan.stages[j];
         if (!g.forward) continue;
+        // the last stage is run forward for its picks alone: not when the caller kept them
+        if (j + 1 == S && kept(g)) continue;
         const void *a = j == 0 ? in : ws + g.a_off;
         void *out = j + 1 < S ? ws + plan.stages[j + 1].a_off : ws + plan.last_out_off;
         const void *res[K_MAX_RES] = {nullptr, nullptr, nullptr, nullptr};
@@ -298,6 +314,7 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         k.g_out = j + 1 == S ? grad_out : ws + plan.stages[j + 1].g_off;
         k.g_in = j == 0 ? grad_in : ws + g.g_off;
         k.idx = g.k.pool.kind == OP_MAXPOOL && !g.k.direct ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
+        if (k.idx && j + 1 == S && kept(g)) k.idx = kept(g);
         k.params = stack->dev_params;
         bool wanted = k.g_in != nullptr;
         for (int32_t r = 0; r < g.n_res; ++r) {

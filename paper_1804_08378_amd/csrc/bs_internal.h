@@ -75,6 +75,7 @@ struct BwdStage {
     int32_t vec = 1, threads = 256;
     int64_t grid = 0;
     bs_stack *forward = nullptr;  // this stage alone as a forward stack (null: its output and picks are not needed)
+    int32_t idx_slot = -1;        // the stack's index output that holds this stage's max-pooling picks, if it has one
     uint64_t a_off = 0;           // workspace offsets: the stage's input (stages >= 1),
     uint64_t idx_off = 0;         // the picks of its max pooling,
     uint64_t g_off = 0;           // the gradient with respect to its input (stages >= 1)

@@ -138,12 +138,16 @@ class _StackFunction(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, module, nhwc, x, *residuals):
-        st = module.plan_for(x.shape, x.dtype, nhwc)
+        st = module.plan_for(x.shape, x.dtype, nhwc, keep_picks=True)
         mf = torch.channels_last if nhwc else torch.contiguous_format
-        out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf)
-        st.run_unchecked(x, list(residuals), out, 0, 0)
+        if st.n_idx:
+            # the last max pooling's picks are kept for the backward pass (saves recomputing them)
+            out, picks = st.run(x, list(residuals))
+        else:
+            out, picks = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf), None
+            st.run_unchecked(x, list(residuals), out, 0, 0)
         ctx.save_for_backward(x, *residuals)
-        ctx.stack, ctx.mf = st, mf
+        ctx.stack, ctx.mf, ctx.picks = st, mf, picks
         return out
 
     @staticmethod
@@ -151,7 +155,7 @@ class _StackFunction(torch.autograd.Function):
         x, *residuals = ctx.saved_tensors
         need = ctx.needs_input_grad  # (module, nhwc, x, *residuals)
         gx, gres = ctx.stack.backward(x, residuals, grad_out.contiguous(memory_format=ctx.mf), need_input_grad=need[2],
-                                      need_residual_grads=list(need[3:]))
+                                      need_residual_grads=list(need[3:]), indices=ctx.picks)
         return (None, None, gx, *gres)
 
 
@@ -187,15 +191,19 @@ class BrainSlugStack(nn.Module):
     def extra_repr(self) -> str:
         return "replaces " + " -> ".join(self.replaced)
 
-    def plan_for(self, shape, dtype: torch.dtype, channels_last: bool = False) -> bs.Stack:
-        """The planned stack for this input shape, dtype and memory format (cached)."""
-        key = (tuple(int(v) for v in shape), dtype, bool(channels_last))
+    def plan_for(self, shape, dtype: torch.dtype, channels_last: bool = False, keep_picks: bool = False) -> bs.Stack:
+        """The planned stack for this input shape, dtype and memory format (cached).  `keep_picks`
+        (the plan autograd records): when the stack's last pooling layer is a max pooling whose
+        picks the backward pass would have to recompute, the forward pass writes them out."""
+        key = (tuple(int(v) for v in shape), dtype, bool(channels_last), bool(keep_picks))
         st = self._plans.get(key)
         if st is None:
             name = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}.get(dtype)
             if name is None:
                 raise TypeError(f"BrainSlugStack supports float32, bfloat16 and float16 tensors, not {dtype}")
             layers = resolve_layers(self.layers, key[0])
+            if keep_picks:
+                layers = self._with_saved_picks(layers, key[0])
             opts = dict(self.plan_opts)
             if channels_last:
                 # channels-last plans have their own kernels: options that pick or tune the
@@ -207,6 +215,20 @@ class BrainSlugStack(nn.Module):
             st.res_shapes = [tuple(v) for v in wl.residual_shapes(layers, key[0])]
             self._plans[key] = st
         return st
+
+    @staticmethod
+    def _with_saved_picks(layers, shape):
+        """`layers` with an index output on the last pooling layer, if that is a max pooling other than
+        2 x 2 / 2 windows that tile the plane (those the backward kernel finds again by itself)."""
+        pools = [i for i, l in enumerate(layers) if l["kind"] in ("maxpool", "avgpool")]
+        if not pools or layers[pools[-1]]["kind"] != "maxpool":
+            return layers
+        i = pools[-1]
+        l = layers[i]
+        h, w = wl.output_shape(layers[:i], shape)[2:]
+        if l["k"] == (2, 2) and l["s"] == (2, 2) and l["p"] == (0, 0) and h % 2 == 0 and w % 2 == 0:
+            return layers
+        return layers[:i] + [dict(l, return_indices=True)] + layers[i + 1:]
 
     def forward(self, x: torch.Tensor, *residuals: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """`residuals`: the second operand of every Add layer of the stack, in layer order.  `out`:
@@ -236,7 +258,7 @@ class BrainSlugStack(nn.Module):
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
             nhwc = not x.is_contiguous() and x.is_contiguous(memory_format=torch.channels_last)
             mf = torch.channels_last if nhwc else torch.contiguous_format
-            st = self.plan_for(x.shape, x.dtype, nhwc)
+            st = self.plan_for(x.shape, x.dtype, nhwc, keep_picks=True)
             for r, want in zip(residuals, st.res_shapes):
                 if r.shape != want or r.dtype != x.dtype or r.device != x.device:
                     raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
@@ -261,7 +283,7 @@ class BrainSlugStack(nn.Module):
                             x, stride = x.contiguous(), 0
                         else:
                             nhwc = True
-            st = self._plans.get((x.shape, x.dtype, nhwc)) or self.plan_for(x.shape, x.dtype, nhwc)
+            st = self._plans.get((x.shape, x.dtype, nhwc, False)) or self.plan_for(x.shape, x.dtype, nhwc)
             mf = torch.channels_last if nhwc else torch.contiguous_format
             if len(residuals) != self.n_residuals:
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")

@@ -103,7 +103,7 @@ int main(int argc, char **argv)
                 if (bp == BS_OK && stages > pi.n_operations + 1) { std::puts("more stages than operations"); return 1; }
                 (void)bs_stack_backward_workspace_bytes(s);
                 float dummy[4] = {0, 0, 0, 0};
-                if (bs_stack_backward(s, dummy, nullptr, dummy, dummy, nullptr, nullptr, 0, nullptr) == BS_OK) {
+                if (bs_stack_backward(s, dummy, nullptr, nullptr, dummy, dummy, nullptr, nullptr, 0, nullptr) == BS_OK) {
                     std::puts("backward succeeded on a host-only plan");
                     return 1;
                 }

@@ -144,10 +144,10 @@ def test_backward_entry_points_without_a_device_plan():
         assert bs.bs_stack_backward_num_stages(h) == -1 and bs.bs_stack_backward_workspace_bytes(h) == 0
         assert _status(bs.bs_stack_plan_backward, h) == 5           # not planned at all
         bs.bs_stack_plan(h, host_only=1)
-        assert _status(bs.bs_stack_backward, h, 16, None, 32, 48, None, 0, 0, 0) == 5
+        assert _status(bs.bs_stack_backward, h, 16, None, None, 32, 48, None, 0, 0, 0) == 5
         bs.bs_stack_plan_backward(h)                                # host-only: stages and sizes, nothing that runs
         assert bs.bs_stack_backward_num_stages(h) == 1
-        assert _status(bs.bs_stack_backward, h, 16, None, 32, 48, None, 0, 0, 0) == 5
+        assert _status(bs.bs_stack_backward, h, 16, None, None, 32, 48, None, 0, 0, 0) == 5
         bs.bs_stack_plan(h, host_only=1)                            # a new plan drops the backward plan
         assert bs.bs_stack_backward_num_stages(h) == -1
         assert _status(bs.bs_stack_plan_backward, None) == 1

@@ -221,27 +221,54 @@ def test_argument_errors():
     dy = torch.zeros(2, 8, 4, 4, device="cuda")
     gx = torch.empty_like(x)
     with pytest.raises(bs.BrainSlugError) as e:  # no backward plan yet
-        bs.bs_stack_backward(st.handle, x.data_ptr(), [], dy.data_ptr(), gx.data_ptr(), [], 0, 0, 0)
+        bs.bs_stack_backward(st.handle, x.data_ptr(), [], None, dy.data_ptr(), gx.data_ptr(), [], 0, 0, 0)
     assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_NOT_PLANNED"]
     st.plan_backward()
     n = bs.bs_stack_backward_workspace_bytes(st.handle)
     ws = torch.empty(n, dtype=torch.uint8, device="cuda")
     with pytest.raises(bs.BrainSlugError) as e:
-        bs.bs_stack_backward(st.handle, x.data_ptr(), [], dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n - 1, 0)
+        bs.bs_stack_backward(st.handle, x.data_ptr(), [], None, dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n - 1, 0)
     assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_WORKSPACE"]
     with pytest.raises(bs.BrainSlugError) as e:  # the gradient over the input
-        bs.bs_stack_backward(st.handle, x.data_ptr(), [], dy.data_ptr(), x.data_ptr(), [], ws.data_ptr(), n, 0)
+        bs.bs_stack_backward(st.handle, x.data_ptr(), [], None, dy.data_ptr(), x.data_ptr(), [], ws.data_ptr(), n, 0)
     assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_ALIAS"]
     with pytest.raises(bs.BrainSlugError) as e:
-        bs.bs_stack_backward(st.handle, x.data_ptr() + 4, [], dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n, 0)
+        bs.bs_stack_backward(st.handle, x.data_ptr() + 4, [], None, dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n, 0)
     assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_ALIGN"]
     with pytest.raises(bs.BrainSlugError) as e:
-        bs.bs_stack_backward(st.handle, 0, [], dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n, 0)
+        bs.bs_stack_backward(st.handle, 0, [], None, dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n, 0)
     assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_NULL"]
     # a new forward plan drops the backward plan
     st.plan()
     assert bs.bs_stack_backward_num_stages(st.handle) == -1
     st.close()
+
+
+@pytest.mark.parametrize("dtype,layout", [("f32", 0), ("f16", 0), ("bf16", 1)])
+def test_saved_indices_replace_the_recomputation(dtype, layout):
+    """The picks kept from the forward pass (index outputs of bs_stack_run) give the same gradient as the
+    recomputed ones, bit for bit; for picks of an inner pooling layer they are simply not needed."""
+    mf = torch.channels_last if layout else torch.contiguous_format
+    for layers, shape in (([wl.bn_params(8, 1), wl.relu(), wl.maxpool(3, 2, 1, True)], (2, 8, 16, 16)),
+                          ([wl.maxpool(3, 1, 1, True), wl.bn_params(8, 2), wl.relu(), wl.maxpool(3, 2, 1, True)], (2, 8, 16, 16))):
+        x, res, dy = _inputs(layers, shape, 3, dtype)
+        st = bs.Stack(layers, shape, dtype).plan(layout=layout).plan_backward()
+        put = lambda a: _dev(a, dtype).contiguous(memory_format=mf)
+        xd, dyd = put(x), put(dy)
+        _, idx = st.run(xd, [])
+        a, _ = st.backward(xd, [], dyd)
+        b, _ = st.backward(xd, [], dyd, indices=idx)
+        c, _ = st.backward(xd, [], dyd, indices=[None] * (len(idx) - 1) + [idx[-1]])
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and torch.equal(a, c)
+        ref, _ = bw.backward_stack(layers, x, [], dy, dtype)
+        _close(b.float().cpu().numpy(), ref, dtype, "saved indices")
+        # wrong picks are trusted, and only misroute: everything to cell 0 of each plane
+        zeros = [torch.zeros_like(t) for t in idx]
+        z, _ = st.backward(xd, [], dyd, indices=zeros)
+        torch.cuda.synchronize()
+        assert torch.isfinite(z.float()).all()
+        st.close()
 
 
 def test_repeated_calls_give_identical_bits():
