@@ -271,6 +271,53 @@ def test_saved_indices_replace_the_recomputation(dtype, layout):
         st.close()
 
 
+def test_forward_and_backward_can_be_captured_in_a_hip_graph_and_replayed():
+    """bs_stack_backward only enqueues kernels (its recomputation passes included): a training step's
+    forward and backward pass of a three-stage stack are captured once and replayed with new operands,
+    eager calls in between; every replay matches the oracle."""
+    c = 6
+    layers = [wl.bn_params(c, 5), wl.add(), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1), wl.bn_params(c, 6), wl.relu()]
+    shape, oshape = (2, c, 24, 32), (2, c, 12, 16)
+    st = bs.Stack(layers, shape, "f32").plan().plan_backward()
+    assert bs.bs_stack_backward_num_stages(st.handle) == 3
+    x_s, r_s, dy_s = (torch.zeros(sh, device="cuda") for sh in (shape, shape, oshape))
+    out, _ = st.alloc_outputs("cuda", False)
+    gx, gr = torch.empty_like(x_s), torch.empty_like(r_s)
+    n = bs.bs_stack_backward_workspace_bytes(st.handle)
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    st.workspace("cuda")
+
+    def step():
+        stream = torch.cuda.current_stream().cuda_stream
+        st.run(x_s, [r_s], out=out, indices=[])
+        bs.bs_stack_backward(st.handle, x_s.data_ptr(), [r_s.data_ptr()], None, dy_s.data_ptr(), gx.data_ptr(), [gr.data_ptr()],
+                             ws.data_ptr(), n, stream)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        x, r, dy = wl.activation(shape, 70 + rep), wl.activation(shape, 80 + rep), wl.activation(oshape, 90 + rep)
+        x_s.copy_(torch.from_numpy(x)); r_s.copy_(torch.from_numpy(r)); dy_s.copy_(torch.from_numpy(dy))
+        gx.zero_(); gr.zero_(); ws.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_x, (ref_r,) = bw.backward_stack(layers, x, [r], dy)
+        _close(gx.cpu().numpy(), ref_x, "f32", f"replay {rep} grad_x")
+        _close(gr.cpu().numpy(), ref_r, "f32", f"replay {rep} grad_residual")
+        a, (b,) = st.backward(x_s, [r_s], dy_s)  # eager call between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(a, gx) and torch.equal(b, gr)
+    del graph
+    st.close()
+
+
 def test_repeated_calls_give_identical_bits():
     """A gather has one summation order: two runs agree bit for bit (no atomics anywhere)."""
     layers = _stacks(6)["halo_stress"]
