@@ -197,6 +197,22 @@ BS_DEV void store_row(const BwdK &k, int j, uint32_t off, int32_t adds, const fl
         }
 }
 
+// VEC consecutive int32 picks starting at element `off` (a multiple of VEC).
+template <int VEC>
+BS_DEV void load_picks(const int32_t *idx, uint32_t off, int32_t (&v)[VEC])
+{
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            const int4 t = *reinterpret_cast<const int4 *>(idx + off + 4 * q);
+            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = idx[off + e];
+    }
+}
+
 // KH, KW, SH, SW, P: the pooling window, strides and padding (the same in both directions) when
 // they are compiled in (KH == 0: read from the argument block).  With them the windows over a
 // lane's cells are a fixed set -- NOH rows of NOW windows, and which cells each window holds is
@@ -256,21 +272,47 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
             const int32_t ow0 = iw0 / SW + CQ;
 #pragma unroll
             for (int a = 0; a < NOH; ++a) {
-                Raw<DT, 1> graw[NOW];
+                float gv[NOW];
                 int32_t pick[NOW];
                 const int32_t oh = oh_lo + a;
+                const uint32_t orow = obase + (uint32_t)(min(oh, k.Ho - 1) * k.Wo);
+                if constexpr (SW == 1 && NOW == VEC + 2) {
+                    // stride 1 (the output row is as long as the input row: checked at launch): windows
+                    // iw0 - 1 .. iw0 + VEC; the middle VEC of them are one aligned vector
+                    const Raw<DT, VEC> mid = load_raw<DT, VEC>(k.g_out, orow + (uint32_t)iw0);
+                    const Raw<DT, 1> left = load_raw<DT, 1>(k.g_out, orow + (uint32_t)max(iw0 - 1, 0));
+                    const Raw<DT, 1> right = load_raw<DT, 1>(k.g_out, orow + (uint32_t)min(iw0 + VEC, k.Wo - 1));
+                    if (is_max) {
+                        int32_t pm[VEC];
+                        load_picks<VEC>(k.idx, orow + (uint32_t)iw0, pm);
 #pragma unroll
-                for (int b = 0; b < NOW; ++b) {
-                    const uint32_t o = obase + (uint32_t)(min(oh, k.Ho - 1) * k.Wo + min(max(ow0 + b, 0), k.Wo - 1));
-                    graw[b] = load_raw<DT, 1>(k.g_out, o);
-                    pick[b] = is_max ? k.idx[o] : 0;
+                        for (int e = 0; e < VEC; ++e) pick[1 + e] = pm[e];
+                        pick[0] = k.idx[orow + (uint32_t)max(iw0 - 1, 0)];
+                        pick[VEC + 1] = k.idx[orow + (uint32_t)min(iw0 + VEC, k.Wo - 1)];
+                    }
+                    float gm[VEC], g1[1];
+                    unpack<DT, VEC>(mid, gm);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) gv[1 + e] = gm[e];
+                    unpack<DT, 1>(left, g1);
+                    gv[0] = g1[0];
+                    unpack<DT, 1>(right, g1);
+                    gv[VEC + 1] = g1[0];
+                } else {
+#pragma unroll
+                    for (int b = 0; b < NOW; ++b) {
+                        const uint32_t o = orow + (uint32_t)min(max(ow0 + b, 0), k.Wo - 1);
+                        float g1[1];
+                        unpack<DT, 1>(load_raw<DT, 1>(k.g_out, o), g1);
+                        gv[b] = g1[0];
+                        pick[b] = is_max ? k.idx[o] : 0;
+                    }
                 }
 #pragma unroll
                 for (int b = 0; b < NOW; ++b) {
                     const int32_t ow = ow0 + b;
                     const bool in = oh <= oh_hi && ow >= 0 && ow < k.Wo;
-                    float g[1];
-                    unpack<DT, 1>(graw[b], g);
+                    const float g[1] = {gv[b]};
                     const int w0 = (CQ + b) * SW - P;  // a constant once the loop is unrolled
                     if (is_max) {
                         const int32_t d = pick[b] - cell0;
@@ -432,21 +474,6 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 // vectors and a window's gradient and picks as one vector each (the VEC channels of the output
 // pixel), so every access of a wave is contiguous.
 // =============================================================================
-template <int VEC>
-BS_DEV void load_picks(const int32_t *idx, uint32_t off, int32_t (&v)[VEC])
-{
-    if constexpr (VEC % 4 == 0) {
-#pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-            const int4 t = *reinterpret_cast<const int4 *>(idx + off + 4 * q);
-            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
-        }
-    } else {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) v[e] = idx[off + e];
-    }
-}
-
 template <int DT, int VEC>
 __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
 {
@@ -576,7 +603,7 @@ static void launch_stage(const BwdK &k, dim3 g, dim3 b, hipStream_t st)
     // the compiled-in instances assume whole vectors per row and VEC a multiple of the stride
     const bool w33p1 = p.kind != 0 && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && VEC > 1;
     if (w33p1 && p.sh == 2 && p.sw == 2) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2, 1><<<g, b, 0, st>>>(k);
-    else if (w33p1 && p.sh == 1 && p.sw == 1) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1, 1><<<g, b, 0, st>>>(k);
+    else if (w33p1 && p.sh == 1 && p.sw == 1 && k.Wo == k.W) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1, 1><<<g, b, 0, st>>>(k);
     else bwd_stage_kernel<DT, VEC, 0, 0, 0, 0, 0><<<g, b, 0, st>>>(k);
 }
 
