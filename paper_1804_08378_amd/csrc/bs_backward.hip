@@ -298,6 +298,25 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
                     gv[0] = g1[0];
                     unpack<DT, 1>(right, g1);
                     gv[VEC + 1] = g1[0];
+                } else if constexpr (SW == 2 && CQ == 0 && VEC >= 2 && NOW == VEC / 2 + 1) {
+                    // stride 2 (the output row is half the input row: checked at launch): windows
+                    // iw0 / 2 .. iw0 / 2 + VEC / 2; all but the last are one aligned vector
+                    constexpr int HV = VEC / 2;
+                    const Raw<DT, HV> mid = load_raw<DT, HV>(k.g_out, orow + (uint32_t)ow0);
+                    const Raw<DT, 1> right = load_raw<DT, 1>(k.g_out, orow + (uint32_t)min(ow0 + HV, k.Wo - 1));
+                    if (is_max) {
+                        int32_t pm[HV];
+                        load_picks<HV>(k.idx, orow + (uint32_t)ow0, pm);
+#pragma unroll
+                        for (int e = 0; e < HV; ++e) pick[e] = pm[e];
+                        pick[HV] = k.idx[orow + (uint32_t)min(ow0 + HV, k.Wo - 1)];
+                    }
+                    float gm[HV], g1[1];
+                    unpack<DT, HV>(mid, gm);
+#pragma unroll
+                    for (int e = 0; e < HV; ++e) gv[e] = gm[e];
+                    unpack<DT, 1>(right, g1);
+                    gv[HV] = g1[0];
                 } else {
 #pragma unroll
                     for (int b = 0; b < NOW; ++b) {
@@ -602,7 +621,7 @@ static void launch_stage(const BwdK &k, dim3 g, dim3 b, hipStream_t st)
     const PoolK &p = k.pool;
     // the compiled-in instances assume whole vectors per row and VEC a multiple of the stride
     const bool w33p1 = p.kind != 0 && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && VEC > 1;
-    if (w33p1 && p.sh == 2 && p.sw == 2) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2, 1><<<g, b, 0, st>>>(k);
+    if (w33p1 && p.sh == 2 && p.sw == 2 && 2 * k.Wo == k.W) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2, 1><<<g, b, 0, st>>>(k);
     else if (w33p1 && p.sh == 1 && p.sw == 1 && k.Wo == k.W) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1, 1><<<g, b, 0, st>>>(k);
     else bwd_stage_kernel<DT, VEC, 0, 0, 0, 0, 0><<<g, b, 0, st>>>(k);
 }
