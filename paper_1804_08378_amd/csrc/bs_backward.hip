@@ -493,7 +493,9 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 // vectors and a window's gradient and picks as one vector each (the VEC channels of the output
 // pixel), so every access of a wave is contiguous.
 // =============================================================================
-template <int DT, int VEC>
+// NOH, NOW: compile-time bounds on the windows over one pixel (ceil(kh / sh) x ceil(kw / sw)),
+// 0 = loops with run-time bounds.  With them all windows' gradients and picks are requested at once.
+template <int DT, int VEC, int NOH, int NOW>
 __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -528,6 +530,37 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
         const int32_t cell = ih * k.W + iw;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s[e] = 0.0f;
+        if constexpr (NOH > 0) {
+            Raw<DT, VEC> graw[NOH][NOW];
+            int32_t pick[NOH][NOW][VEC];
+#pragma unroll
+            for (int a = 0; a < NOH; ++a)
+#pragma unroll
+                for (int b = 0; b < NOW; ++b) {
+                    // windows beyond the range are read at a clamped (valid) pixel and not used
+                    const uint32_t o = (obase + (uint32_t)(min(oh_lo + a, k.Ho - 1) * k.Wo + min(ow_lo + b, k.Wo - 1))) * (uint32_t)k.C +
+                                       (uint32_t)c0;
+                    graw[a][b] = load_raw<DT, VEC>(k.g_out, o);
+                    if (is_max) load_picks<VEC>(k.idx, o, pick[a][b]);
+                }
+#pragma unroll
+            for (int a = 0; a < NOH; ++a)
+#pragma unroll
+                for (int b = 0; b < NOW; ++b) {
+                    const int32_t oh = oh_lo + a, ow = ow_lo + b;
+                    const bool in = oh <= oh_hi && ow <= ow_hi;
+                    float g[VEC];
+                    unpack<DT, VEC>(graw[a][b], g);
+                    if (is_max) {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) s[e] += (in && pick[a][b][e] == cell) ? g[e] : 0.0f;
+                    } else {
+                        const float inv = in ? bwd_avg_inv(p, k.H, k.W, min(oh, k.Ho - 1), min(ow, k.Wo - 1)) : 0.0f;
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) s[e] += g[e] * inv;
+                    }
+                }
+        } else
         for (int32_t oh = oh_lo; oh <= oh_hi; ++oh)
             for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
                 // 0 <= oh < Ho, 0 <= ow < Wo: an output pixel; its VEC channels c0 .. c0 + VEC - 1
@@ -648,11 +681,15 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
                          p.ph != 0 || p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo))
             return BS_ERR_UNSUPPORTED;
         if (!k.direct && p.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
+        // windows over one pixel: at most ceil(kh / sh) x ceil(kw / sw); 2 x 2 and 3 x 3 are compiled in
+        const int32_t noh = p.kind != 0 ? (p.kh + p.sh - 1) / p.sh : 0, now = p.kind != 0 ? (p.kw + p.sw - 1) / p.sw : 0;
 #define BS_LAUNCH_NHWC(DT, V)                                                          \
     do {                                                                               \
         if (k.direct && !has_add) bwd_direct2_nhwc_kernel<DT, V, 0><<<g, b, 0, st>>>(k); \
         else if (k.direct) bwd_direct2_nhwc_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k); \
-        else bwd_stage_nhwc_kernel<DT, V><<<g, b, 0, st>>>(k);                         \
+        else if (noh == 2 && now == 2) bwd_stage_nhwc_kernel<DT, V, 2, 2><<<g, b, 0, st>>>(k); \
+        else if (noh == 3 && now == 3) bwd_stage_nhwc_kernel<DT, V, 3, 3><<<g, b, 0, st>>>(k); \
+        else bwd_stage_nhwc_kernel<DT, V, 0, 0><<<g, b, 0, st>>>(k);                   \
     } while (0)
         if (dtype == BS_F32) { if (vec == 4) BS_LAUNCH_NHWC(DT_F32, 4); else BS_LAUNCH_NHWC(DT_F32, 1); }
         else if (dtype == BS_BF16) { if (vec == 8) BS_LAUNCH_NHWC(DT_BF16, 8); else BS_LAUNCH_NHWC(DT_BF16, 1); }
