@@ -425,6 +425,8 @@ class Stack:
         self.out_shape = bs_stack_output_shape(self.handle)
         self.n_res = bs_stack_num_residuals(self.handle)
         self.n_idx = bs_stack_num_index_outputs(self.handle)
+        self.res_shapes = [bs_stack_residual_shape(self.handle, i) for i in range(self.n_res)]
+        self.idx_shapes = [bs_stack_index_shape(self.handle, i) for i in range(self.n_idx)]
         self._workspace = None
         self._workspace_bytes = 0
         self._fast = None
@@ -455,6 +457,7 @@ class Stack:
         bs_stack_plan_backward(self.handle)
         self._bwd_planned = True
         self._bwd_workspace = None
+        self._bwd_workspace_bytes = bs_stack_backward_workspace_bytes(self.handle)
         return self
 
     def backward(self, x, residuals, grad_out, need_input_grad=True, need_residual_grads=None, stream=None, indices=None):
@@ -476,12 +479,12 @@ class Stack:
         if len(residuals) != self.n_res:
             raise ValueError(f"the stack has {self.n_res} residual operands")
         for i, r in enumerate(residuals):
-            if tuple(r.shape) != bs_stack_residual_shape(self.handle, i) or r.dtype != dt or not r.is_contiguous(memory_format=mf):
+            if tuple(r.shape) != self.res_shapes[i] or r.dtype != dt or not r.is_contiguous(memory_format=mf):
                 raise ValueError("residuals must be dense tensors of their Add layer's shape, the stack's dtype and memory layout")
         need_res = [True] * self.n_res if need_residual_grads is None else list(need_residual_grads)
         gx = torch.empty_like(x, memory_format=mf) if need_input_grad else None
         gres = [torch.empty_like(r, memory_format=mf) if need else None for r, need in zip(residuals, need_res)]
-        n = bs_stack_backward_workspace_bytes(self.handle)
+        n = self._bwd_workspace_bytes
         if n and (self._bwd_workspace is None or self._bwd_workspace.numel() < n or self._bwd_workspace.device != x.device):
             self._bwd_workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
         ws = self._bwd_workspace if n else None
@@ -490,7 +493,7 @@ class Stack:
             if len(indices) != self.n_idx:
                 raise ValueError(f"the stack has {self.n_idx} index outputs")
             for i, t in enumerate(indices):
-                if t is not None and (tuple(t.shape) != bs_stack_index_shape(self.handle, i) or t.dtype != torch.int32 or
+                if t is not None and (tuple(t.shape) != self.idx_shapes[i] or t.dtype != torch.int32 or
                                       not t.is_contiguous(memory_format=mf)):
                     raise ValueError("saved indices must be the int32 index outputs of run()")
         idx = [t.data_ptr() if t is not None else 0 for t in indices] if indices else None
@@ -516,7 +519,7 @@ class Stack:
         import torch
         mf = torch.channels_last if self.layout == BS_LAYOUT_NHWC else torch.contiguous_format
         out = torch.empty(self.out_shape, dtype=self.torch_dtype(), device=device, memory_format=mf)
-        idx = [torch.empty(bs_stack_index_shape(self.handle, i), dtype=torch.int32, device=device, memory_format=mf)
+        idx = [torch.empty(self.idx_shapes[i], dtype=torch.int32, device=device, memory_format=mf)
                for i in range(self.n_idx)] if indices else []
         return out, idx
 
