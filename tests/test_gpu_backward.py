@@ -171,6 +171,52 @@ def test_planes_that_are_no_whole_number_of_vectors(dtype):
     check(layers, (4, 6, 28, 28), dtype, "flat stage behind a pooling stage")
 
 
+def _random_stack(rng, c, h, w):
+    """A random valid stack of 1..9 layers (all layer kinds, odd windows, strides, padding, ceil mode, up to four
+    residual operands); every pooling output at least 1 x 1."""
+    layers, adds = [], 0
+    kinds = ["bn", "relu", "leaky", "clamp", "add", "max", "max", "avg", "avg"]
+    for _ in range(int(rng.integers(1, 10))):
+        kind = rng.choice(kinds)
+        if kind in ("max", "avg"):
+            k = (int(rng.integers(1, 6)), int(rng.integers(1, 6)))
+            st = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+            p = (int(rng.integers(0, k[0] // 2 + 1)), int(rng.integers(0, k[1] // 2 + 1)))
+            ceil = bool(rng.integers(0, 3) == 0)
+            ho, wo = wl.pool_out(h, k[0], st[0], p[0], ceil), wl.pool_out(w, k[1], st[1], p[1], ceil)
+            if h + 2 * p[0] < k[0] or w + 2 * p[1] < k[1] or ho < 1 or wo < 1:
+                continue
+            layers.append(wl.maxpool(k, st, p, False, ceil_mode=ceil) if kind == "max"
+                          else wl.avgpool(k, st, p, bool(rng.integers(0, 2)), ceil_mode=ceil))
+            h, w = ho, wo
+        elif kind == "bn":
+            layers.append(wl.bn_params(c, int(rng.integers(0, 1000))))
+        elif kind == "relu":
+            layers.append(wl.relu())
+        elif kind == "leaky":
+            layers.append(wl.leaky_relu(float(rng.choice([0.01, 0.1, 0.3]))))
+        elif kind == "clamp":
+            layers.append(wl.clamp(float(rng.choice([-1.0, 0.0, -0.25])), float(rng.choice([0.5, 1.0, 6.0]))))
+        elif adds < 4:
+            layers.append(wl.add())
+            adds += 1
+    return layers or [wl.relu()]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_stacks_match_the_oracle(seed):
+    """Seeded random stacks on random small shapes, all three storage types, both memory layouts."""
+    rng = np.random.default_rng(5000 + seed)
+    for case in range(10):
+        n, c = int(rng.integers(1, 4)), int(rng.choice([1, 3, 4, 5, 8, 16]))
+        h = int(rng.choice([5, 7, 8, 12, 16, 20, 24, 31]))
+        w = int(rng.choice([5, 8, 9, 12, 16, 24, 32, 40]))
+        dtype = ("f32", "bf16", "f16")[(seed + case) % 3]
+        layers = _random_stack(rng, c, h, w)
+        opts = [dict(), dict(layout=bs.BS_LAYOUT_NHWC), dict(jit=-1)][int(rng.integers(0, 3))]
+        check(layers, (n, c, h, w), dtype, f"random/{seed}.{case} {[l['kind'] for l in layers]}", seed=100 * seed + case, **opts)
+
+
 def test_long_lists_are_cut_into_stages():
     c = 4
     # 20 element-wise operations (more than one argument block holds), 6 Adds (more than one stage's residual slots)
