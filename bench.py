@@ -242,6 +242,12 @@ def frontend_network(batch=32, reps=10,
             dtype = getattr(torch, dname)
             torch.manual_seed(0)
             ref = zoo.randomize_batchnorm(make[name]()).cuda().eval().to(dtype)
+            # frozen BatchNorm layers: running statistics (eval mode) and no gradient for their affine
+            # parameters either, on both sides (a rewritten model has them folded into its stacks)
+            for m in ref.modules():
+                if isinstance(m, torch.nn.BatchNorm2d):
+                    m.weight.requires_grad_(False)
+                    m.bias.requires_grad_(False)
             size = 299 if name.startswith("inception") else 224
             xs = [torch.randn(batch, 3, size, size, device="cuda").to(dtype) for _ in range(2)]
             if channels_last:

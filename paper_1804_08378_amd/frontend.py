@@ -134,7 +134,9 @@ def resolve_layers(layers: List[dict], shape) -> List[dict]:
 class _StackFunction(torch.autograd.Function):
     """A stack as one node of the autograd graph: the forward pass keeps only the stack's operands
     (no intermediate tensor exists to keep), the backward pass recomputes what it needs from them
-    (`bs_stack_backward`).  BatchNorm is the inference-mode layer, its parameters get no gradient."""
+    (`bs_stack_backward`).  BatchNorm is the inference-mode layer with its parameters folded in when the
+    stack was built: they get no gradient (frozen BatchNorm; freeze them in the original model as well
+    when comparing the two)."""
 
     @staticmethod
     def forward(ctx, module, nhwc, x, *residuals):
