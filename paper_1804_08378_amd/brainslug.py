@@ -562,8 +562,9 @@ class Stack:
                                  batch_stride(out), idx, wsp, wsn, st)
         return out, indices
 
-    def run_unchecked(self, x, residuals, out, in_batch_stride=0, out_batch_stride=0):
-        """`bs_stack_run_strided` with as little Python in the way as possible (no index outputs;
+    def run_unchecked(self, x, residuals, out, in_batch_stride=0, out_batch_stride=0, indices=None):
+        """`bs_stack_run_strided` with as little Python in the way as possible (`indices`: None, or one
+        int32 tensor of the plan's layout per index output;
         the residuals dense tensors of the plan's layout; `x` / `out` dense, or channel slices with
         `in_batch_stride` / `out_batch_stride` elements between their images): for callers that have validated
         shapes, dtypes and layouts themselves -- the front-end does, once per call.  The library
@@ -581,10 +582,34 @@ class Stack:
         # a fresh pointer array per call: the library reads it while the interpreter lock is released
         res = res_type(*[r.data_ptr() for r in residuals]) if residuals else None
         st = raw_stream(dev) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
-        rc = fn(h, x.data_ptr(), in_batch_stride, res, out.data_ptr(), out_batch_stride, None, wsp, wsn, st)
+        idx = (C.c_void_p * len(indices))(*[t.data_ptr() for t in indices]) if indices else None
+        rc = fn(h, x.data_ptr(), in_batch_stride, res, out.data_ptr(), out_batch_stride, idx, wsp, wsn, st)
         if rc != 0:
             _check(rc, "bs_stack_run_strided")
         return out
+
+    def backward_unchecked(self, x, residuals, grad_out, grad_x, grad_residuals, indices=None):
+        """`bs_stack_backward` with as little Python in the way as possible: dense tensors of the plan's
+        layout and the stack's dtype that the caller has validated and allocated (`grad_x` and entries
+        of `grad_residuals` may be None: not wanted; `indices`: the forward pass's index outputs or
+        None).  The library still checks alignment, aliasing and the workspace."""
+        import torch
+        if not self._bwd_planned:
+            self.plan_backward()
+        n = self._bwd_workspace_bytes
+        if n and (self._bwd_workspace is None or self._bwd_workspace.device != x.device):
+            self._bwd_workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
+        ptr = C.c_void_p * max(1, self.n_res)
+        res = ptr(*[r.data_ptr() for r in residuals]) if residuals else None
+        gres = ptr(*[g.data_ptr() if g is not None else None for g in grad_residuals]) if grad_residuals else None
+        idx = (C.c_void_p * len(indices))(*[t.data_ptr() if t is not None else None for t in indices]) if indices else None
+        raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+        st = raw_stream(x.device.index) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        rc = load().bs_stack_backward(self.handle, x.data_ptr(), res, idx, grad_out.data_ptr(),
+                                      grad_x.data_ptr() if grad_x is not None else None, gres,
+                                      self._bwd_workspace.data_ptr() if n else None, n, st)
+        if rc != 0:
+            _check(rc, "bs_stack_backward")
 
     def _run_nhwc(self, x, residuals, out, indices, stream):
         """A channels-last plan: every tensor is in torch's channels_last memory format."""

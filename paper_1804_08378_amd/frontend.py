@@ -142,12 +142,11 @@ class _StackFunction(torch.autograd.Function):
     def forward(ctx, module, nhwc, x, *residuals):
         st = module.plan_for(x.shape, x.dtype, nhwc, keep_picks=True)
         mf = torch.channels_last if nhwc else torch.contiguous_format
-        if st.n_idx:
-            # the last max pooling's picks are kept for the backward pass (saves recomputing them)
-            out, picks = st.run(x, list(residuals))
-        else:
-            out, picks = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf), None
-            st.run_unchecked(x, list(residuals), out, 0, 0)
+        out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf)
+        # the last max pooling's picks, where the plan writes them, are kept for the backward pass
+        # (saves recomputing them)
+        picks = [torch.empty(sh, dtype=torch.int32, device=x.device, memory_format=mf) for sh in st.idx_shapes] or None
+        st.run_unchecked(x, list(residuals), out, 0, 0, picks)
         ctx.save_for_backward(x, *residuals)
         ctx.stack, ctx.mf, ctx.picks = st, mf, picks
         return out
@@ -156,8 +155,11 @@ class _StackFunction(torch.autograd.Function):
     def backward(ctx, grad_out):
         x, *residuals = ctx.saved_tensors
         need = ctx.needs_input_grad  # (module, nhwc, x, *residuals)
-        gx, gres = ctx.stack.backward(x, residuals, grad_out.contiguous(memory_format=ctx.mf), need_input_grad=need[2],
-                                      need_residual_grads=list(need[3:]), indices=ctx.picks)
+        mf = ctx.mf
+        gx = torch.empty_like(x, memory_format=mf) if need[2] else None
+        gres = [torch.empty_like(r, memory_format=mf) if wanted else None for r, wanted in zip(residuals, need[3:])]
+        # operands validated in forward(); the upstream gradient has the output's shape and dtype
+        ctx.stack.backward_unchecked(x, residuals, grad_out.contiguous(memory_format=mf), gx, gres, ctx.picks)
         return (None, None, gx, *gres)
 
 
