@@ -373,19 +373,24 @@ def test_repeated_calls_give_identical_bits():
     assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
-@pytest.mark.parametrize("name,dtype", [("vgg_a", "f32"), ("vgg_c", "bf16"), ("resnet_tail", "f16"), ("halo_stress", "f32")])
-def test_benchmark_sizes_on_sampled_images(name, dtype):
-    """Whole tensors at the benchmark sizes on the GPU; images are independent, so the oracle checks
-    a sample of them (first, one inside, last) in full."""
+@pytest.mark.parametrize("name,dtype,layout", [("vgg_a", "f32", 0), ("vgg_c", "bf16", 0), ("resnet_tail", "f16", 0), ("halo_stress", "f32", 0),
+                                               ("resnet_stem", "f16", 0), ("vgg_a", "f32", 1), ("resnet_stem", "f16", 1),
+                                               ("resnet_tail", "bf16", 1), ("densenet_trans", "f32", 1)])
+def test_benchmark_sizes_on_sampled_images(name, dtype, layout):
+    """Whole tensors at the benchmark sizes on the GPU, in the launch configuration the benchmark times,
+    row-major and channels-last; images are independent, so the oracle checks a sample of them (first,
+    one inside, last) in full."""
     layers, shape, _ = wl.build(name, 0, None, False)
-    print(f"[backward] {name} full size shape={shape} dtype={dtype}", flush=True)
+    print(f"[backward] {name} full size shape={shape} dtype={dtype} layout={layout}", flush=True)
     td = TORCH[dtype]
+    mf = torch.channels_last if layout else torch.contiguous_format
     g = torch.Generator(device="cuda").manual_seed(5)
-    x = torch.randn(shape, device="cuda", generator=g).to(td)
+    rnd = lambda sh: torch.randn(sh, device="cuda", generator=g).to(td).contiguous(memory_format=mf)
+    x = rnd(shape)
     out_shape = wl.output_shape(layers, shape)
-    dy = torch.randn(out_shape, device="cuda", generator=g).to(td)
-    res = [torch.randn(s, device="cuda", generator=g).to(td) for s in wl.residual_shapes(layers, shape)]
-    st = bs.Stack(layers, shape, dtype).plan().plan_backward()
+    dy = rnd(out_shape)
+    res = [rnd(s) for s in wl.residual_shapes(layers, shape)]
+    st = bs.Stack(layers, shape, dtype).plan(layout=layout).plan_backward()
     gx, gres = st.backward(x, res, dy)
     torch.cuda.synchronize()
     for n in (0, shape[0] // 2 + 1, shape[0] - 1):
