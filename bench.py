@@ -641,6 +641,13 @@ def main():
                 sb.launch("fused")
             torch.cuda.synchronize()
             log("probe", name, "algorithmic bytes per launch", sb.bytes)
+            # the backward pass of the same stack (input and upstream gradient in, input gradient out)
+            dy, gx = torch.randn_like(sb.out[0]), torch.empty_like(sb.x[0])
+            sb.fused.plan_backward()
+            for _ in range(args.probe):
+                sb.fused.backward_unchecked(sb.x[0], sb.res[0], dy, gx, [])
+            torch.cuda.synchronize()
+            log("probe", name, "backward: algorithmic bytes per launch", 2 * sb.x[0].numel() * 4 + dy.numel() * 4)
         return
 
     stacks = [StackBench(n, "f32") for n in wl.VGG_STACKS]
