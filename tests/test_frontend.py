@@ -759,6 +759,45 @@ def test_gradients_flow_through_rewritten_models():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("channels_last", [False, True])
+def test_gradients_flow_through_inception_and_squeezenet(channels_last):
+    """Branches, concatenations, stride-1 average pooling, ceil-mode pooling and lone activations under
+    autograd, row-major and channels_last: input and convolution-weight gradients of the rewritten model
+    against the original's (float32; 2-norms, see the test above).  The reference is always the row-major
+    original: this PyTorch build's own channels_last `avg_pool2d` backward (3 x 3, stride 1, padding 1) is
+    off by the size of the gradient itself against its CPU float64 result (measured: 0.86 .. 1.5 of the
+    largest gradient on four shapes, where its row-major kernel and the stacks agree with float64 to 1e-7)."""
+    def rel(a, b):
+        return ((a.float() - b.float()).norm() / b.float().norm().clamp_min(1e-30)).item()
+
+    torch.manual_seed(0)
+    for make, size in ((lambda: zoo.inception_v3(0.25, 10), 139), (lambda: zoo.squeezenet("1.1", 0.5, 10), 96)):
+        ref = zoo.randomize_batchnorm(make()).cuda().eval()
+        x = torch.randn(2, 3, size, size, device="cuda")
+        opt = copy.deepcopy(ref)
+        xo = x
+        if channels_last:
+            opt = opt.to(memory_format=torch.channels_last)
+            xo = x.contiguous(memory_format=torch.channels_last)
+        opt = fe.optimize_graph(opt, lone_activations=True)
+        assert len(opt.optimized_stacks) > 10
+        with torch.no_grad():
+            w = torch.randn_like(ref(x))
+        grads = {}
+        for key, model, xin in (("ref", ref, x), ("opt", opt, xo)):
+            xi = xin.clone().requires_grad_(True)
+            model.zero_grad(set_to_none=True)
+            (model(xi) * w).sum().backward()
+            grads[key] = (xi.grad, {n: p.grad for n, p in model.named_parameters() if p.dim() == 4 and p.grad is not None})
+        assert rel(grads["opt"][0], grads["ref"][0]) <= 2e-2
+        assert len(grads["opt"][1]) == len(grads["ref"][1]) > 10
+        cat = lambda g: torch.cat([g[n].flatten() for n in grads["ref"][1]])
+        assert rel(cat(grads["opt"][1]), cat(grads["ref"][1])) <= 2e-2
+        for st in opt.optimized_stacks:
+            st.close()
+
+
+@pytest.mark.gpu
 def test_stack_under_autograd_keeps_only_its_operands():
     layers = [zoo.randomize_batchnorm(nn.BatchNorm2d(8)), nn.ReLU(), nn.MaxPool2d(3, 2, 1)]
     stack = fe.BrainSlugStack(layers).cuda().eval()
