@@ -322,7 +322,7 @@ def frontend_network(batch=32, reps=10,
                     % (batch, "channels_last" if channels_last else "NCHW"), "rows": rows}
 
 
-def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50", "densenet121"),
+def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50", "densenet121", "inception_v3"),
                       dtypes=("float32", "float16"), channels_last=False):
     """Fine-tuning step with frozen BatchNorm layers (eval mode, autograd on: the paper's outlook,
     Section 7): forward pass, a scalar loss, backward pass to every convolution and linear weight.
