@@ -375,7 +375,7 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 // vectors; a work-group takes nthr * U consecutive ones, lane t the vectors t, t + nthr, ...:
 // U independent loads of every operand in flight per lane.
 // =============================================================================
-template <int DT, int VEC, int U>
+template <int DT, int VEC, int U, int NR>
 __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
 {
     const uint32_t nthr = blockDim.x;
@@ -405,16 +405,16 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
         ar[u] = load_raw<DT, VEC, true>(k.a, offs[u]);
         gr[u] = load_raw<DT, VEC, true>(k.g_out, offs[u]);
     }
-    float x[U][VEC], t[U][VEC], r[K_MAX_RES][U][VEC], s[U][VEC];
+    float x[U][VEC], t[U][VEC], r[NR ? NR : 1][U][VEC], s[U][VEC];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         unpack<DT, VEC>(ar[u], x[u]);
         unpack<DT, VEC>(gr[u], s[u]);
     }
-    const int32_t adds = ew_sweep<DT, VEC, U>(k, cs, offs, x, t, r, k.flat ? nfirst : nullptr);
+    const int32_t adds = ew_sweep<DT, VEC, U, false, NR>(k, cs, offs, x, t, r, k.flat ? nfirst : nullptr);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (live[u]) store_row<DT, VEC, U>(k, u, offs[u], adds, s[u], t, r);
+        if (live[u]) store_row<DT, VEC, U, NR>(k, u, offs[u], adds, s[u], t, r);
 }
 
 // =============================================================================
@@ -742,10 +742,20 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     if (k.pool.kind == 0 && vec == full) {
         // no pooling, whole vectors: K_BWD_EW_U vectors per lane (the grid was sized for one per lane)
         const dim3 gu((uint32_t)((grid + K_BWD_EW_U - 1) / K_BWD_EW_U));
-        if (dtype == BS_F32) bwd_ew_kernel<DT_F32, 4, K_BWD_EW_U><<<gu, b, 0, st>>>(k);
-        else if (dtype == BS_BF16) bwd_ew_kernel<DT_BF16, 8, K_BWD_EW_U><<<gu, b, 0, st>>>(k);
-        else if (dtype == BS_F16) bwd_ew_kernel<DT_F16, 8, K_BWD_EW_U><<<gu, b, 0, st>>>(k);
+        // instances that keep 0, 1 or K_MAX_RES residual gradients in registers, by the stage's Adds
+        int32_t n_add = 0;
+        for (int32_t j = 0; j < k.n_ew; ++j) n_add += k.ew[j].kind == OP_ADD;
+#define BS_LAUNCH_EW(DT, V)                                                                        \
+    do {                                                                                           \
+        if (n_add == 0) bwd_ew_kernel<DT, V, K_BWD_EW_U, 0><<<gu, b, 0, st>>>(k);                  \
+        else if (n_add == 1) bwd_ew_kernel<DT, V, K_BWD_EW_U, 1><<<gu, b, 0, st>>>(k);             \
+        else bwd_ew_kernel<DT, V, K_BWD_EW_U, K_MAX_RES><<<gu, b, 0, st>>>(k);                     \
+    } while (0)
+        if (dtype == BS_F32) BS_LAUNCH_EW(DT_F32, 4);
+        else if (dtype == BS_BF16) BS_LAUNCH_EW(DT_BF16, 8);
+        else if (dtype == BS_F16) BS_LAUNCH_EW(DT_F16, 8);
         else return BS_ERR_UNSUPPORTED;
+#undef BS_LAUNCH_EW
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error(e);
