@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 // =============================================================================
 // NOH, NOW: compile-time bounds on the windows over one pixel (ceil(kh / sh) x ceil(kw / sw)),
 // 0 = loops with run-time bounds.  With them all windows' gradients and picks are requested at once.
-template <int DT, int VEC, int NOH, int NOW>
+template <int DT, int VEC, int NOH, int NOW, int NR = K_MAX_RES>
 __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -510,11 +510,11 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
     const int32_t c0 = (int32_t)(cv * VEC);
     const uint32_t off = pix * (uint32_t)k.C + (uint32_t)c0;  // < N*H*W*C: i < total, or 0
 
-    float x[1][VEC], t[1][VEC], r[K_MAX_RES][1][VEC];
+    float x[1][VEC], t[1][VEC], r[NR ? NR : 1][1][VEC];
     unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x[0]);
     const uint32_t offs[1] = {off};
     const int32_t cs[1] = {c0};
-    const int32_t adds = ew_sweep<DT, VEC, 1, true>(k, cs, offs, x, t, r);
+    const int32_t adds = ew_sweep<DT, VEC, 1, true, NR>(k, cs, offs, x, t, r);
 
     float s[VEC];
     const PoolK &p = k.pool;
@@ -579,7 +579,7 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
                 }
             }
     }
-    if (live) store_row<DT, VEC, 1>(k, 0, off, adds, s, t, r);
+    if (live) store_row<DT, VEC, 1, NR>(k, 0, off, adds, s, t, r);
 }
 
 // Disjoint 2 x 2 windows that tile the plane, channels-last: a lane owns VEC channels of one
@@ -668,8 +668,9 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     if (k.n_ew < 0 || k.n_ew > K_BWD_EW) return BS_ERR_UNSUPPORTED;
     const dim3 g((uint32_t)grid), b((uint32_t)threads);
     // a stage without Add gets the instances that keep no residual gradients in registers
-    bool has_add = false;
-    for (int32_t j = 0; j < k.n_ew; ++j) has_add = has_add || k.ew[j].kind == OP_ADD;
+    int32_t n_add = 0;
+    for (int32_t j = 0; j < k.n_ew; ++j) n_add += k.ew[j].kind == OP_ADD;
+    const bool has_add = n_add > 0;
     if (k.nhwc) {
         // a lane per (pixel or window, channel vector): the divisors must be the ones the kernels assume
         if ((vec != 1 && vec != full) || k.C % vec != 0 || (int64_t)k.div_wv.d * vec != k.C ||
@@ -689,6 +690,8 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         else if (k.direct) bwd_direct2_nhwc_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k); \
         else if (noh == 2 && now == 2) bwd_stage_nhwc_kernel<DT, V, 2, 2><<<g, b, 0, st>>>(k); \
         else if (noh == 3 && now == 3) bwd_stage_nhwc_kernel<DT, V, 3, 3><<<g, b, 0, st>>>(k); \
+        else if (n_add == 0) bwd_stage_nhwc_kernel<DT, V, 0, 0, 0><<<g, b, 0, st>>>(k); \
+        else if (n_add == 1) bwd_stage_nhwc_kernel<DT, V, 0, 0, 1><<<g, b, 0, st>>>(k); \
         else bwd_stage_nhwc_kernel<DT, V, 0, 0><<<g, b, 0, st>>>(k);                   \
     } while (0)
         if (dtype == BS_F32) { if (vec == 4) BS_LAUNCH_NHWC(DT_F32, 4); else BS_LAUNCH_NHWC(DT_F32, 1); }
@@ -743,8 +746,6 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         // no pooling, whole vectors: K_BWD_EW_U vectors per lane (the grid was sized for one per lane)
         const dim3 gu((uint32_t)((grid + K_BWD_EW_U - 1) / K_BWD_EW_U));
         // instances that keep 0, 1 or K_MAX_RES residual gradients in registers, by the stage's Adds
-        int32_t n_add = 0;
-        for (int32_t j = 0; j < k.n_ew; ++j) n_add += k.ew[j].kind == OP_ADD;
 #define BS_LAUNCH_EW(DT, V)                                                                        \
     do {                                                                                           \
         if (n_add == 0) bwd_ew_kernel<DT, V, K_BWD_EW_U, 0><<<gu, b, 0, st>>>(k);                  \
