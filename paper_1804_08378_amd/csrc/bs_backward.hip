@@ -218,7 +218,7 @@ BS_DEV void load_picks(const int32_t *idx, uint32_t off, int32_t (&v)[VEC])
 // lane's cells are a fixed set -- NOH rows of NOW windows, and which cells each window holds is
 // known at compile time -- so a row's gradients and picks are requested at once instead of one
 // dependent round trip per window, and only the (window, cell) pairs that exist are summed.
-template <int DT, int VEC, int KH, int KW, int SH, int SW, int P>
+template <int DT, int VEC, int KH, int KW, int SH, int SW, int P, int NR = K_MAX_RES>
 __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -234,11 +234,11 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
     const uint32_t off = rowi * (uint32_t)k.W + (uint32_t)iw0;  // < N*C*H*W: i < total, or 0
 
     // ---- 1. forward through the element-wise list, collecting derivative products
-    float x[1][VEC], t[1][VEC], r[K_MAX_RES][1][VEC];
+    float x[1][VEC], t[1][VEC], r[NR ? NR : 1][1][VEC];
     unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x[0]);
     const uint32_t offs[1] = {off};
     const int32_t cs[1] = {c};
-    const int32_t adds = ew_sweep<DT, VEC, 1>(k, cs, offs, x, t, r);
+    const int32_t adds = ew_sweep<DT, VEC, 1, false, NR>(k, cs, offs, x, t, r);
 
     // ---- 2. gradient with respect to the list's output
     float s[VEC];
@@ -366,7 +366,7 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
     }
 
     // ---- 3. results
-    if (live) store_row<DT, VEC, 1>(k, 0, off, adds, s, t, r);
+    if (live) store_row<DT, VEC, 1, NR>(k, 0, off, adds, s, t, r);
 }
 
 // =============================================================================
@@ -652,10 +652,17 @@ template <int DT, int VEC>
 static void launch_stage(const BwdK &k, dim3 g, dim3 b, hipStream_t st)
 {
     const PoolK &p = k.pool;
+    bool has_add = false;
+    for (int32_t j = 0; j < k.n_ew; ++j) has_add = has_add || k.ew[j].kind == OP_ADD;
     // the compiled-in instances assume whole vectors per row and VEC a multiple of the stride
     const bool w33p1 = p.kind != 0 && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && VEC > 1;
-    if (w33p1 && p.sh == 2 && p.sw == 2 && 2 * k.Wo == k.W) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2, 1><<<g, b, 0, st>>>(k);
-    else if (w33p1 && p.sh == 1 && p.sw == 1 && k.Wo == k.W) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1, 1><<<g, b, 0, st>>>(k);
+    if (w33p1 && p.sh == 2 && p.sw == 2 && 2 * k.Wo == k.W) {
+        if (has_add) bwd_stage_kernel<DT, VEC, 3, 3, 2, 2, 1><<<g, b, 0, st>>>(k);
+        else bwd_stage_kernel<DT, VEC, 3, 3, 2, 2, 1, 0><<<g, b, 0, st>>>(k);
+    } else if (w33p1 && p.sh == 1 && p.sw == 1 && k.Wo == k.W) {
+        if (has_add) bwd_stage_kernel<DT, VEC, 3, 3, 1, 1, 1><<<g, b, 0, st>>>(k);
+        else bwd_stage_kernel<DT, VEC, 3, 3, 1, 1, 1, 0><<<g, b, 0, st>>>(k);
+    }
     else bwd_stage_kernel<DT, VEC, 0, 0, 0, 0, 0><<<g, b, 0, st>>>(k);
 }
 
