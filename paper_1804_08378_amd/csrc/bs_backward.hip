@@ -695,7 +695,9 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     do {                                                                               \
         if (k.direct && !has_add) bwd_direct2_nhwc_kernel<DT, V, 0><<<g, b, 0, st>>>(k); \
         else if (k.direct) bwd_direct2_nhwc_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k); \
+        else if (noh == 2 && now == 2 && n_add == 0) bwd_stage_nhwc_kernel<DT, V, 2, 2, 0><<<g, b, 0, st>>>(k); \
         else if (noh == 2 && now == 2) bwd_stage_nhwc_kernel<DT, V, 2, 2><<<g, b, 0, st>>>(k); \
+        else if (noh == 3 && now == 3 && n_add == 0) bwd_stage_nhwc_kernel<DT, V, 3, 3, 0><<<g, b, 0, st>>>(k); \
         else if (noh == 3 && now == 3) bwd_stage_nhwc_kernel<DT, V, 3, 3><<<g, b, 0, st>>>(k); \
         else if (n_add == 0) bwd_stage_nhwc_kernel<DT, V, 0, 0, 0><<<g, b, 0, st>>>(k); \
         else if (n_add == 1) bwd_stage_nhwc_kernel<DT, V, 0, 0, 1><<<g, b, 0, st>>>(k); \
