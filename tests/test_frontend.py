@@ -706,6 +706,25 @@ def test_rewritten_model_matches_the_original_and_the_oracle(dtype):
         s.close()
 
 
+def test_plans_recorded_by_autograd_keep_the_last_max_poolings_picks():
+    """The plan autograd records writes the picks of the stack's last pooling layer when that is a max
+    pooling the backward pass would otherwise recompute; 2 x 2 / 2 windows that tile the plane, average
+    pooling and inner pooling layers are left alone."""
+    keep = fe.BrainSlugStack._with_saved_picks
+    flags = lambda layers, shape: [l.get("return_indices") for l in keep(fe.resolve_layers(layers, shape), shape) if l["kind"] == "maxpool"]
+    stem = fe.BrainSlugStack([nn.BatchNorm2d(4), nn.ReLU(), nn.MaxPool2d(3, 2, 1)]).layers
+    assert flags(stem, (1, 4, 16, 16)) == [True]
+    vgg = fe.BrainSlugStack([nn.BatchNorm2d(4), nn.ReLU(), nn.MaxPool2d(2, 2)]).layers
+    assert flags(vgg, (1, 4, 16, 16)) == [False]
+    assert flags(vgg, (1, 4, 15, 16)) == [True]           # an odd plane is not tiled by 2 x 2 windows
+    two = fe.BrainSlugStack([nn.MaxPool2d(3, 1, 1), nn.BatchNorm2d(4), nn.ReLU(), nn.MaxPool2d(3, 2, 1), nn.ReLU()]).layers
+    assert flags(two, (1, 4, 16, 16)) == [False, True]    # only the last pooling layer
+    avg_last = fe.BrainSlugStack([nn.MaxPool2d(3, 2, 1), nn.ReLU(), nn.AvgPool2d(2, 2)]).layers
+    assert flags(avg_last, (1, 4, 16, 16)) == [False]
+    # the caller's layer list is not modified
+    assert [l.get("return_indices") for l in stem if l["kind"] == "maxpool"] == [False]
+
+
 @pytest.mark.gpu
 def test_gradients_flow_through_rewritten_models():
     """Fine-tuning with frozen BatchNorm layers (eval mode, autograd on): the rewritten model gives
