@@ -677,7 +677,6 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
     // a stage without Add gets the instances that keep no residual gradients in registers
     int32_t n_add = 0;
     for (int32_t j = 0; j < k.n_ew; ++j) n_add += k.ew[j].kind == OP_ADD;
-    const bool has_add = n_add > 0;
     if (k.nhwc) {
         // a lane per (pixel or window, channel vector): the divisors must be the ones the kernels assume
         if ((vec != 1 && vec != full) || k.C % vec != 0 || (int64_t)k.div_wv.d * vec != k.C ||
@@ -693,7 +692,8 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         const int32_t noh = p.kind != 0 ? (p.kh + p.sh - 1) / p.sh : 0, now = p.kind != 0 ? (p.kw + p.sw - 1) / p.sw : 0;
 #define BS_LAUNCH_NHWC(DT, V)                                                          \
     do {                                                                               \
-        if (k.direct && !has_add) bwd_direct2_nhwc_kernel<DT, V, 0><<<g, b, 0, st>>>(k); \
+        if (k.direct && n_add == 0) bwd_direct2_nhwc_kernel<DT, V, 0><<<g, b, 0, st>>>(k); \
+        else if (k.direct && n_add == 1) bwd_direct2_nhwc_kernel<DT, V, 1><<<g, b, 0, st>>>(k); \
         else if (k.direct) bwd_direct2_nhwc_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k); \
         else if (noh == 2 && now == 2 && n_add == 0) bwd_stage_nhwc_kernel<DT, V, 2, 2, 0><<<g, b, 0, st>>>(k); \
         else if (noh == 2 && now == 2) bwd_stage_nhwc_kernel<DT, V, 2, 2><<<g, b, 0, st>>>(k); \
@@ -731,18 +731,17 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         if ((p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 2 || p.kw != 2 || p.sh != 2 || p.sw != 2 || p.ph != 0 ||
             p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo || vec != full)
             return BS_ERR_UNSUPPORTED;
-        if (dtype == BS_F32) {
-            if (has_add) bwd_direct2_kernel<DT_F32, 4, K_MAX_RES><<<g, b, 0, st>>>(k);
-            else bwd_direct2_kernel<DT_F32, 4, 0><<<g, b, 0, st>>>(k);
-        } else if (dtype == BS_BF16) {
-            if (has_add) bwd_direct2_kernel<DT_BF16, 8, K_MAX_RES><<<g, b, 0, st>>>(k);
-            else bwd_direct2_kernel<DT_BF16, 8, 0><<<g, b, 0, st>>>(k);
-        } else if (dtype == BS_F16) {
-            if (has_add) bwd_direct2_kernel<DT_F16, 8, K_MAX_RES><<<g, b, 0, st>>>(k);
-            else bwd_direct2_kernel<DT_F16, 8, 0><<<g, b, 0, st>>>(k);
-        } else {
-            return BS_ERR_UNSUPPORTED;
-        }
+#define BS_LAUNCH_DIRECT(DT, V)                                                                \
+    do {                                                                                       \
+        if (n_add == 0) bwd_direct2_kernel<DT, V, 0><<<g, b, 0, st>>>(k);                      \
+        else if (n_add == 1) bwd_direct2_kernel<DT, V, 1><<<g, b, 0, st>>>(k);                 \
+        else bwd_direct2_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k);                         \
+    } while (0)
+        if (dtype == BS_F32) BS_LAUNCH_DIRECT(DT_F32, 4);
+        else if (dtype == BS_BF16) BS_LAUNCH_DIRECT(DT_BF16, 8);
+        else if (dtype == BS_F16) BS_LAUNCH_DIRECT(DT_F16, 8);
+        else return BS_ERR_UNSUPPORTED;
+#undef BS_LAUNCH_DIRECT
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error(e);
