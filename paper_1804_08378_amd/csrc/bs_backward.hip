@@ -44,11 +44,11 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // CL: channels-last -- the VEC cells of a row are consecutive channels c[j] .. c[j] + VEC - 1 of one
 // pixel (all rows hold the same channels), so BatchNorm parameters are per-cell vectors.
 // NR: residual gradients kept (K_MAX_RES, or 0 for a stage without Add: no registers for them).
-// nfirst (row-major only): cells of row j that lie in channel c[j]; the rest lie in the next channel
-// (a vector that straddles two planes).  Null: every cell of row j lies in channel c[j].
-template <int DT, int VEC, int R, bool CL = false, int NR = K_MAX_RES>
-BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
-                        float (&r)[NR ? NR : 1][R][VEC], const uint32_t *nfirst = nullptr)
+// FLAT (row-major only): nfirst[j] cells of row j lie in channel c[j], the rest in the next channel
+// (a vector that straddles two planes).  Otherwise every cell of row j lies in channel c[j].
+template <int DT, int VEC, int R, bool CL, int NR, bool FLAT>
+BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC],
+                             float (&t)[R][VEC], float (&r)[NR ? NR : 1][R][VEC], const uint32_t (&nfirst)[R])
 {
 #pragma unroll
     for (int j = 0; j < R; ++j)
@@ -119,7 +119,7 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
                 for (int j = 0; j < R; ++j) {
                     sc[j] = k.params[arg + c[j]];
                     sh[j] = k.params[arg + k.C + c[j]];
-                    if (nfirst) {
+                    if constexpr (FLAT) {
                         const int32_t cn = c[j] + 1 == k.C ? 0 : c[j] + 1;
                         sc1[j] = k.params[arg + cn];
                         sh1[j] = k.params[arg + k.C + cn];
@@ -132,7 +132,7 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
                 for (int j = 0; j < R; ++j)
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
-                        const bool first = !nfirst || (uint32_t)e < nfirst[j];
+                        const bool first = !FLAT || (uint32_t)e < nfirst[j];
                         f[j][e] = first ? sc[j] : sc1[j];
                         x[j][e] = round_store<DT>(__builtin_fmaf(x[j][e], f[j][e], first ? sh[j] : sh1[j]));
                     }
@@ -174,6 +174,14 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
             }
     }
     return adds;
+}
+
+template <int DT, int VEC, int R, bool CL = false, int NR = K_MAX_RES>
+BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC], float (&t)[R][VEC],
+                        float (&r)[NR ? NR : 1][R][VEC])
+{
+    const uint32_t none[R] = {};
+    return ew_sweep_impl<DT, VEC, R, CL, NR, false>(k, c, off, x, t, r, none);
 }
 
 // Write grad_in = s * t and grad_residual[n] = s * r[n] for one register row.
@@ -411,7 +419,8 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
         unpack<DT, VEC>(ar[u], x[u]);
         unpack<DT, VEC>(gr[u], s[u]);
     }
-    const int32_t adds = ew_sweep<DT, VEC, U, false, NR>(k, cs, offs, x, t, r, k.flat ? nfirst : nullptr);
+    const int32_t adds = k.flat ? ew_sweep_impl<DT, VEC, U, false, NR, true>(k, cs, offs, x, t, r, nfirst)
+                                : ew_sweep_impl<DT, VEC, U, false, NR, false>(k, cs, offs, x, t, r, nfirst);
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (live[u]) store_row<DT, VEC, U, NR>(k, u, offs[u], adds, s[u], t, r);
