@@ -45,7 +45,7 @@ constexpr int K_MAX_EW = 6;       // element-wise operations attached to one lev
 constexpr int K_MAX_STREAM_EW = 16;
 constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
-constexpr int K_STREAM_U = 4;     // 128-bit vectors per lane in stream_kernel
+constexpr int K_STREAM_U = 2;     // 128-bit vectors per lane in stream_kernel (measured on MI355X: 1 is 3..9 points of HBM peak slower, 4 is 1..3 slower with 16-bit storage)
 constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
 // Elements per lane and row (the lane's column block) of the sliding-window kernels for 16-bit
 // storage: one 128-bit load, as for float32 (4).  Measured on MI355X, 64-bit blocks (twice the

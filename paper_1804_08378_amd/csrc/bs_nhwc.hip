@@ -519,7 +519,7 @@ static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 bl
 {
     const PoolK &p = k.pool;
     if (p.kind == 0) {
-        nhwc_stream_kernel<DT, VEC, 4><<<grid, block, 0, st>>>(k);
+        nhwc_stream_kernel<DT, VEC, K_STREAM_U><<<grid, block, 0, st>>>(k);
         return BS_OK;
     }
     if (k.cv_group > 0) {
