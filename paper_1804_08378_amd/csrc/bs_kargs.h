@@ -54,7 +54,7 @@ constexpr int K_ROWS_VEC16 = 8;
 constexpr int K_ROWS2_VEC16 = 8;
 constexpr int K_ROWS2_VEC32 = 4;  // float32 in the two-level kernel (8, two loads per row, measured 5 % slower: registers)
 constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
-constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel
+constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel (2 measured 1..2 % slower on the VGG stacks)
 constexpr int K_PLANE_WALK_CELLS = 16;  // whole-plane pooling: planes up to this many cells are walked in global
                                         // memory by one lane each, larger ones are staged through LDS
 
