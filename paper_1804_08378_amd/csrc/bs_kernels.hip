@@ -591,15 +591,24 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         break;
     }
     case BS_VARIANT_POOL_DIRECT: {
-        if (q.vec != (dtype == BS_F32 ? 4 : 8) || (int64_t)q.direct.div_wv.d * q.vec != q.direct.W) return BS_ERR_UNSUPPORTED;
+        // column blocks the instances exist for: one 128-bit vector, or one 64-bit vector with 16-bit storage
+        if ((q.vec != (dtype == BS_F32 ? 4 : 8) && !(dtype != BS_F32 && q.vec == 4)) || q.vec % q.direct.pool.kw != 0 ||
+            (int64_t)q.direct.div_wv.d * q.vec != q.direct.W)
+            return BS_ERR_UNSUPPORTED;
         PoolDirectK k = q.direct;
         k.in = in; k.out = out; k.params = s->dev_params;
         k.in_extra = in_extra; k.out_extra = out_extra;
         for (int j = 0; j < K_MAX_RES; ++j) k.res[j] = rp[j];
         k.idx = ip[0];
-        if (dtype == BS_BF16) launch_direct<DT_BF16, 8>(k, grid, block, st);
-        else if (dtype == BS_F16) launch_direct<DT_F16, 8>(k, grid, block, st);
-        else launch_direct<DT_F32, 4>(k, grid, block, st);
+        if (dtype == BS_BF16) {
+            if (q.vec == 8) launch_direct<DT_BF16, 8>(k, grid, block, st);
+            else launch_direct<DT_BF16, 4>(k, grid, block, st);
+        } else if (dtype == BS_F16) {
+            if (q.vec == 8) launch_direct<DT_F16, 8>(k, grid, block, st);
+            else launch_direct<DT_F16, 4>(k, grid, block, st);
+        } else {
+            launch_direct<DT_F32, 4>(k, grid, block, st);
+        }
         break;
     }
     case BS_VARIANT_PLANE_POOL: {

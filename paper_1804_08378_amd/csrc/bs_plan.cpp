@@ -298,16 +298,26 @@ static int32_t count_pools(const bs_stack *s, int32_t first_op, int32_t n_ops)
     return n;
 }
 
+// Column block (elements per lane and row) of the disjoint-window kernel for a pooling operation: one
+// 128-bit vector, or -- 16-bit storage and rows that are a multiple of 4 but not of 8 elements, the
+// 28 x 28 planes of VGG and DenseNet -- one 64-bit vector; 0: rows that are neither.
+static int32_t direct_vec(const bs_stack *s, const Op &op)
+{
+    const int32_t full = s->dtype == BS_F32 ? 4 : 8;
+    if (op.in_w % full == 0) return full;
+    return s->dtype != BS_F32 && op.in_w % 4 == 0 ? 4 : 0;
+}
+
 static bool direct_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops)
 {
     if (count_pools(s, first_op, n_ops) != 1) return false;
-    const int32_t vec = vec_of(s);
     for (int32_t i = first_op; i < first_op + n_ops; ++i) {
         const Op &op = s->ops[i];
         if (op_is_elementwise(op.kind)) continue;
         if (op.kh != op.sh || op.kw != op.sw || op.ph != 0 || op.pw != 0) return false;
         if (op.ceil) return false;  // its last windows overhang the plane: the kernel reads whole windows
-        if (op.in_w % vec != 0 || vec % op.kw != 0) return false;
+        const int32_t vec = direct_vec(s, op);
+        if (vec == 0 || vec % op.kw != 0) return false;
         if (op.kh > 4 || (op.kw != 1 && op.kw != 2 && op.kw != 4 && op.kw != 8)) return false;
     }
     int32_t pre = 0, post = 0;
@@ -546,20 +556,21 @@ static void plan_direct(const bs_stack *s, Sequence &q, bool whole_plane = false
     q.variant = whole_plane ? BS_VARIANT_PLANE_POOL : BS_VARIANT_POOL_DIRECT;
     PoolDirectK &k = q.direct;
     k = PoolDirectK{};
-    const int32_t vec = vec_of(s);
-    q.vec = vec;
+    int32_t vec = vec_of(s);
     bool seen = false;
     for (int32_t i = q.first_op; i < q.first_op + q.n_ops; ++i) {
         const Op &op = s->ops[i];
         if (!op_is_elementwise(op.kind)) {
             k.pool = make_pool(op, nullptr, q);
             k.H = op.in_h; k.W = op.in_w; k.Ho = op.out_h; k.Wo = op.out_w;
+            if (!whole_plane) vec = direct_vec(s, op);  // non-zero: direct_applicable said so
             seen = true;
         } else if (op.kind != OP_AVGNORM) {
             if (seen) fill_ew(s, op, q, k.post[k.n_post++]);
             else fill_ew(s, op, q, k.pre[k.n_pre++]);
         }
     }
+    q.vec = vec;
     k.C = (int32_t)q.in_shape[1];
     const int64_t planes = q.in_shape[0] * q.in_shape[1];
     if (whole_plane) {

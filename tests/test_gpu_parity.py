@@ -459,6 +459,27 @@ def test_tracing_ranges_do_not_change_results():
     assert r.returncode == 0 and "traced run ok" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
 
 
+# ------------------------------------------------------------------ 64-bit column blocks
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_sixteen_bit_rows_of_four_mod_eight_use_the_disjoint_window_kernel(dtype):
+    """16-bit storage, rows that are a multiple of 4 but not of 8 elements (the 28 x 28 planes of VGG and
+    DenseNet): the disjoint-window kernel with one 64-bit vector per lane and row, not the tile kernel."""
+    c = 6
+    for layers, shape in (([wl.bn_params(c, 1), wl.relu(), wl.maxpool(2, 2, 0, True)], (3, c, 28, 28)),
+                          ([wl.bn_params(c, 2), wl.relu(), wl.avgpool(2, 2), wl.bn_params(c, 3), wl.add()], (2, c, 28, 28)),
+                          ([wl.add(), wl.leaky_relu(0.1), wl.maxpool((3, 4), (3, 4), 0, True), wl.relu()], (2, c, 9, 12)),
+                          ([wl.avgpool((2, 1), (2, 1)), wl.clamp(-0.5, 0.5)], (2, c, 10, 20))):
+        x = wl.activation(shape, 7, dtype)
+        res = [wl.activation(s, 8 + i, dtype) for i, s in enumerate(wl.residual_shapes(layers, shape))]
+        info = check(layers, x, res, dtype, f"64-bit column blocks {shape}")
+        q = info["sequences"][0]
+        assert [v["variant_name"] for v in info["sequences"]] == ["pool_direct"]
+        # one lane per output row and block of four input columns
+        ho = wl.output_shape([l for l in layers if l["kind"] in ("maxpool", "avgpool")], shape)[2]
+        lanes = shape[0] * shape[1] * ho * (shape[3] // 4)
+        assert 0 <= q["grid"] * q["threads_per_group"] - lanes < q["threads_per_group"]
+
+
 # ------------------------------------------------------------------ HIP graph capture
 def test_run_can_be_captured_in_a_hip_graph_and_replayed():
     """bs_stack_run only enqueues kernels on the caller's stream (no allocation, no
