@@ -174,13 +174,14 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
                 g.k.div_wv = make_fastdiv((uint32_t)(g.k.C / g.vec));
                 g.k.div_w = make_fastdiv((uint32_t)(g.k.direct ? g.k.Wo : g.k.W));
             } else {
-                g.vec = g.k.W % full == 0 ? full : 1;
+                // one 128-bit vector per lane; 16-bit rows of 4 mod 8 elements (28 x 28 planes): one 64-bit vector
+                g.vec = g.k.W % full == 0 ? full : (stack->dtype != BS_F32 && g.k.W % 4 == 0 ? 4 : 1);
                 // disjoint 2 x 2 windows that tile the plane: the kernel that owns whole windows
-                g.k.direct = tiles2x2 && g.vec == full;
+                g.k.direct = tiles2x2 && g.vec > 1;
                 // no pooling and rows that are no whole vectors (the 28 x 28, 14 x 14, 7 x 7 planes of
                 // 16-bit networks): vectors over the whole tensor, which may straddle two planes
                 const int64_t hw = (int64_t)g.k.H * g.k.W;
-                if (p.kind == 0 && g.vec == 1 && numel(g.in_shape) % (uint64_t)full == 0 && hw >= full) {
+                if (p.kind == 0 && g.vec != full && numel(g.in_shape) % (uint64_t)full == 0 && hw >= full) {
                     g.vec = full;
                     g.k.flat = 1;
                     g.k.div_w = make_fastdiv((uint32_t)hw);

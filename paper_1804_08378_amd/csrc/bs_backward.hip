@@ -729,7 +729,7 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         if (k.pool.kind != 0 || vec != full || (int64_t)k.div_w.d != (int64_t)k.H * k.W || (int64_t)k.H * k.W < vec ||
             (int64_t)k.div_c.d != k.C || (int64_t)grid * threads < (int64_t)k.total)
             return BS_ERR_UNSUPPORTED;
-    } else if ((vec != 1 && vec != full) || k.W % vec != 0 || (int64_t)k.div_wv.d * vec != k.W ||
+    } else if ((vec != 1 && vec != full && !(dtype != BS_F32 && vec == 4)) || k.W % vec != 0 || (int64_t)k.div_wv.d * vec != k.W ||
                (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_c.d != k.C ||
                (int64_t)grid * threads < (int64_t)k.total) {
         return BS_ERR_UNSUPPORTED;
@@ -738,7 +738,7 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         const PoolK &p = k.pool;
         // what the kernel assumes: 2 x 2 windows, stride 2, no padding, tiling the plane; whole vectors
         if ((p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 2 || p.kw != 2 || p.sh != 2 || p.sw != 2 || p.ph != 0 ||
-            p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo || vec != full)
+            p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo || vec < 2)
             return BS_ERR_UNSUPPORTED;
 #define BS_LAUNCH_DIRECT(DT, V)                                                                \
     do {                                                                                       \
@@ -747,8 +747,8 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         else bwd_direct2_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k);                         \
     } while (0)
         if (dtype == BS_F32) BS_LAUNCH_DIRECT(DT_F32, 4);
-        else if (dtype == BS_BF16) BS_LAUNCH_DIRECT(DT_BF16, 8);
-        else if (dtype == BS_F16) BS_LAUNCH_DIRECT(DT_F16, 8);
+        else if (dtype == BS_BF16) { if (vec == 8) BS_LAUNCH_DIRECT(DT_BF16, 8); else BS_LAUNCH_DIRECT(DT_BF16, 4); }
+        else if (dtype == BS_F16) { if (vec == 8) BS_LAUNCH_DIRECT(DT_F16, 8); else BS_LAUNCH_DIRECT(DT_F16, 4); }
         else return BS_ERR_UNSUPPORTED;
 #undef BS_LAUNCH_DIRECT
         const hipError_t e = hipGetLastError();
@@ -786,9 +786,11 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         else launch_stage<DT_F32, 1>(k, g, b, st);
     } else if (dtype == BS_BF16) {
         if (vec == 8) launch_stage<DT_BF16, 8>(k, g, b, st);
+        else if (vec == 4) launch_stage<DT_BF16, 4>(k, g, b, st);
         else launch_stage<DT_BF16, 1>(k, g, b, st);
     } else if (dtype == BS_F16) {
         if (vec == 8) launch_stage<DT_F16, 8>(k, g, b, st);
+        else if (vec == 4) launch_stage<DT_F16, 4>(k, g, b, st);
         else launch_stage<DT_F16, 1>(k, g, b, st);
     } else {
         return BS_ERR_UNSUPPORTED;

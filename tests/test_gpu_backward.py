@@ -217,6 +217,20 @@ def test_random_stacks_match_the_oracle(seed):
         check(layers, (n, c, h, w), dtype, f"random/{seed}.{case} {[l['kind'] for l in layers]}", seed=100 * seed + case, **opts)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_sixteen_bit_rows_of_four_mod_eight(dtype):
+    """28 x 28 and 12-wide planes with 16-bit storage: one 64-bit vector per lane (2 x 2 windows owned whole,
+    the 3 x 3 gathers with the window compiled in, the generic gather), not one cell per lane."""
+    c = 6
+    for layers in ([wl.bn_params(c, 1), wl.relu(), wl.maxpool(2, 2)],
+                   [wl.add(), wl.bn_params(c, 2), wl.relu(), wl.avgpool(2, 2), wl.bn_params(c, 3)],
+                   [wl.bn_params(c, 4), wl.relu(), wl.maxpool(3, 2, 1)],
+                   [wl.avgpool(3, 1, 1, True), wl.add(), wl.maxpool(3, 1, 1), wl.relu()],
+                   [wl.leaky_relu(0.1), wl.maxpool((2, 4), (2, 4)), wl.add()]):
+        check(layers, (2, c, 28, 28), dtype, f"28 x 28 {[l['kind'] for l in layers]}")
+        check(layers, (3, c, 10, 12), dtype, f"10 x 12 {[l['kind'] for l in layers]}", seed=5)
+
+
 def test_long_lists_are_cut_into_stages():
     c = 4
     # 20 element-wise operations (more than one argument block holds), 6 Adds (more than one stage's residual slots)
