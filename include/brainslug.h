@@ -44,6 +44,7 @@ extern "C" {
 #define BS_MAX_LAYERS 256      /* layers per stack                                  */
 #define BS_MAX_RESIDUALS 16    /* BS_ADD layers per stack                           */
 #define BS_MAX_INDEX_OUTPUTS 16 /* max-pool layers with return_indices per stack    */
+#define BS_STATIC_WORKSPACE_BYTES (64ull << 20) /* size of the library-owned workspace of bs_stack_run_static */
 
 typedef enum bs_status {
     BS_OK = 0,
@@ -294,6 +295,29 @@ BS_API uint64_t bs_stack_workspace_bytes(const bs_stack *stack);
 BS_API bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,
                               void *out, int32_t *const *indices, void *workspace,
                               uint64_t workspace_bytes, void *stream);
+
+/*
+ * bs_stack_run for callers that cannot allocate device memory and therefore have no workspace
+ * to pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The intermediate tensors between sequences go to a library-owned array of
+ * BS_STATIC_WORKSPACE_BYTES (64 MiB) that is part of the library's device code: every GPU the
+ * library runs on holds one copy from the moment the code is loaded there until the process
+ * ends.  bs_stack_plan looks up the array's address on its device; this call allocates and frees
+ * nothing (no hipMalloc / hipFree, no allocating library routine), never synchronises, and only
+ * enqueues the sequence kernels, exactly those of bs_stack_run.
+ *   in, residuals, out, indices, stream   as in bs_stack_run (caller-owned, dense)
+ * A stack whose bs_stack_workspace_bytes() exceeds BS_STATIC_WORKSPACE_BYTES is refused with
+ * BS_ERR_WORKSPACE (nothing is enqueued); a stack that is one sequence uses no workspace at all.
+ * All calls on one GPU share that GPU's array.  It keeps the last call's contents; nothing in
+ * it has to start at zero, because every sequence writes its whole output before the next one
+ * reads it.  Two calls that need the workspace and overlap in time on one GPU (different
+ * streams, or a graph replay beside an eager call) race on it: the caller must order them.
+ * Errors: those of bs_stack_run.
+ */
+BS_API bs_status bs_stack_run_static(const bs_stack *stack, const void *in, const void *const *residuals,
+                                     void *out, int32_t *const *indices, void *stream);
+/* BS_STATIC_WORKSPACE_BYTES of the loaded library. */
+BS_API uint64_t bs_static_workspace_capacity(void);
 
 /*
  * bs_stack_run for an input and / or an output that is a channel slice of a larger NCHW

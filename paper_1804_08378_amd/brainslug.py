@@ -98,6 +98,9 @@ _SIGNATURES = {
     "bs_stack_workspace_bytes": (C.c_uint64, [C.c_void_p]),
     "bs_stack_run": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
                                C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_stack_run_static": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
+                                      C.POINTER(C.c_void_p), C.c_void_p]),
+    "bs_static_workspace_capacity": (C.c_uint64, []),
     "bs_stack_run_strided": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.c_void_p,
                                        C.c_int64, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
     "bs_stack_check_buffers": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.c_void_p,
@@ -330,6 +333,23 @@ def bs_stack_run(handle, in_ptr, residual_ptrs, out_ptr, index_ptrs, workspace_p
     _check(load().bs_stack_run(C.c_void_p(handle), C.c_void_p(in_ptr or None), res,
                                C.c_void_p(out_ptr or None), idx, C.c_void_p(workspace_ptr or None),
                                int(workspace_bytes), C.c_void_p(stream or None)), "bs_stack_run")
+
+
+def bs_stack_run_static(handle, in_ptr, residual_ptrs, out_ptr, index_ptrs, stream) -> None:
+    """bs_stack_run on the library's own static workspace; *_ptr are integer device addresses."""
+    res = None
+    if residual_ptrs:
+        res = (C.c_void_p * len(residual_ptrs))(*[C.c_void_p(p or None) for p in residual_ptrs])
+    idx = None
+    if index_ptrs:
+        idx = (C.c_void_p * len(index_ptrs))(*[C.c_void_p(p or None) for p in index_ptrs])
+    _check(load().bs_stack_run_static(C.c_void_p(handle), C.c_void_p(in_ptr or None), res,
+                                      C.c_void_p(out_ptr or None), idx, C.c_void_p(stream or None)),
+           "bs_stack_run_static")
+
+
+def bs_static_workspace_capacity() -> int:
+    return int(load().bs_static_workspace_capacity())
 
 
 def bs_stack_plan_backward(handle) -> None:

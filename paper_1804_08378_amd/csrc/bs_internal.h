@@ -146,6 +146,8 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
                           uint32_t in_extra, uint32_t out_extra, const void *const *res,
                           int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
+// bs_run.cpp: resolve the address of the library's static scratch array on `device` (the current one)
+bs_status static_workspace_prepare(int device);
 // bs_nhwc.hip: channels-last kernels (element-wise, and one pooling step per sequence)
 void nhwc_block(const PoolK &p, int32_t vec, int32_t dtype, int32_t &ohb, int32_t &owb);  // output pixels per lane
 int32_t nhwc_plane_group(int64_t hw, int32_t vec, const PoolK &p, int32_t H, int32_t W, int32_t Ho, int32_t Wo);

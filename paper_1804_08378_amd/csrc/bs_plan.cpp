@@ -1270,6 +1270,10 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (!o.host_only) {
         st = upload_params(stack);
         if (st != BS_OK) return st;
+        // set-up for bs_stack_run_static: find this device's copy of the library's scratch array now,
+        // so that the run call itself touches nothing but the launch queue
+        st = static_workspace_prepare(device);
+        if (st != BS_OK) return st;
         stack->device = device;
         stack->device_planned = true;
     }

@@ -2,13 +2,44 @@
 // sequences of the stack one after the other on the caller's stream.  Intermediate
 // tensors between sequences alternate between the two halves of the workspace.
 // Nothing here synchronises or allocates.
+#include <hip/hip_runtime.h>
+
 #include <cstdint>
+#include <mutex>
 
 #include "bs_internal.h"
 
 using namespace bs;
 
+// Device memory for callers that may not allocate (bs_stack_run_static): the workspace between
+// sequences lives in this array instead of a caller's buffer.  Every GPU the library's code
+// object is loaded on holds its own copy, at its own address, until the process ends.  In host
+// code the name is only a handle for hipGetSymbolAddress; g_scratch_ptr[device] is the memory.
+static __device__ __align__(256) unsigned char scratch[BS_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+constexpr int K_MAX_DEVICES = 64;
+void *g_scratch_ptr[K_MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// Address of `scratch` on `device`, which must be the current device.  Resolved once per device.
+bs_status scratch_address(int device, void **out)
+{
+    if (device < 0 || device >= K_MAX_DEVICES) return BS_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            set_hip_error((int32_t)e);
+            return BS_ERR_HIP;
+        }
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return BS_OK;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -152,6 +183,27 @@ extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const v
                                   uint64_t workspace_bytes, void *stream)
 {
     return run(stack, in, 0, residuals, out, 0, indices, workspace, workspace_bytes, stream);
+}
+
+extern "C" uint64_t bs_static_workspace_capacity(void) { return BS_STATIC_WORKSPACE_BYTES; }
+
+bs_status bs::static_workspace_prepare(int device)
+{
+    void *ptr = nullptr;
+    return scratch_address(device, &ptr);
+}
+
+extern "C" bs_status bs_stack_run_static(const bs_stack *stack, const void *in, const void *const *residuals,
+                                         void *out, int32_t *const *indices, void *stream)
+{
+    if (!stack) return BS_ERR_NULL;
+    if (!stack->planned || !stack->device_planned) return BS_ERR_NOT_PLANNED;
+    if (stack->workspace_bytes > BS_STATIC_WORKSPACE_BYTES) return BS_ERR_WORKSPACE;
+    if (current_device() != stack->device) return BS_ERR_DEVICE;
+    void *ptr = nullptr;  // resolved by bs_stack_plan on this device; here only if that was skipped
+    const bs_status st = scratch_address(stack->device, &ptr);
+    if (st != BS_OK) return st;
+    return run(stack, in, 0, residuals, out, 0, indices, ptr, BS_STATIC_WORKSPACE_BYTES, stream);
 }
 
 extern "C" bs_status bs_stack_run_strided(const bs_stack *stack, const void *in, int64_t in_batch_stride,
