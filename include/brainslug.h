@@ -173,6 +173,11 @@ typedef enum bs_layout {
  *                           every pixel: bs_stack_run_strided takes its batch stride, which
  *                           must be H * W times the larger tensor's channel count.  Index outputs
  *                           hold the same values (ih * W + iw) in channels-last order.
+ *   lane_exchange           sliding-window (BS_VARIANT_POOL_ROWS) sequences on planes whose rows fit one
+ *                           wave as 128-bit column blocks (at most 64 of them): 0 = the lanes pass
+ *                           their edge columns to their neighbours inside the wave (each input
+ *                           element is loaded and computed once); -1 = every lane loads and
+ *                           recomputes the columns next to its block itself, as for wider planes.
  */
 typedef struct bs_plan_options {
     uint64_t max_lds_bytes;
@@ -185,7 +190,8 @@ typedef struct bs_plan_options {
     int32_t host_only;
     int32_t jit;
     int32_t layout;
-    int32_t reserved[3];
+    int32_t lane_exchange;
+    int32_t reserved[2];
 } bs_plan_options;
 
 typedef struct bs_plan_info {

@@ -53,7 +53,7 @@ class bs_plan_options(C.Structure):
                 ("num_cus", C.c_int32), ("breadth_first", C.c_int32), ("force_variant", C.c_int32),
                 ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("planes_per_group", C.c_int32),
                 ("host_only", C.c_int32), ("jit", C.c_int32), ("layout", C.c_int32),
-                ("reserved", C.c_int32 * 3)]
+                ("lane_exchange", C.c_int32), ("reserved", C.c_int32 * 2)]
 
 
 class bs_plan_info(C.Structure):

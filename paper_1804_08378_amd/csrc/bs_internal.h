@@ -129,6 +129,9 @@ inline bool dtype_has_tables(int32_t dtype) { return dtype == BS_F32 || dtype ==
 // Column-block width (elements per lane and row) of the one- / two-level sliding-window kernels.
 inline int32_t rows_vec(int32_t dtype) { return dtype == BS_F32 ? 4 : K_ROWS_VEC16; }
 inline int32_t rows2_vec(int32_t dtype) { return dtype == BS_F32 ? K_ROWS2_VEC32 : K_ROWS2_VEC16; }
+// the same for the kernels whose lanes exchange edge columns
+inline int32_t xrows_vec(int32_t dtype) { return dtype == BS_F32 ? K_XROWS_VEC32 : K_XROWS_VEC16; }
+inline int32_t xrows2_vec(int32_t dtype) { return dtype == BS_F32 ? K_XROWS2_VEC32 : K_XROWS2_VEC16; }
 
 // planner (host only)
 bs_status build_operations(bs_stack *s);
@@ -164,6 +167,17 @@ bool rows2_supported(const PoolRows2K &k);
 bool rows2_buildable(const PoolRows2K &k, int32_t vec);
 std::string rows2_expr(const PoolRows2K &k, int32_t dtype, bool want_idx);
 bs_status launch_rows2(const PoolRows2K &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
+// bs_xrows.hip: the sliding-window kernels whose lanes exchange edge columns (rows of at most 64 column
+// blocks); their pre-compiled signatures are those of rows_supported / rows2_supported.
+// *_launchable = the argument block and the launch shape are what the kernel assumes
+bool xrows_buildable(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post, int32_t vec);
+bool xrows2_buildable(const PoolRows2K &k, int32_t vec);
+std::string xrows_expr(const PoolRowsK &k, int32_t dtype, bool want_idx);
+std::string xrows2_expr(const PoolRows2K &k, int32_t dtype, bool want_idx);
+bool xrows_launchable(const PoolRowsK &k, int32_t dtype, int64_t grid, int32_t threads);
+bool xrows2_launchable(const PoolRows2K &k, int32_t dtype, int64_t grid, int32_t threads);
+bs_status launch_xrows(const PoolRowsK &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
+bs_status launch_xrows2(const PoolRows2K &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
 bool lds_fast_path(const LdsSeqK &k);
 bool lds_precompiled(const LdsSeqK &k, int32_t dtype);

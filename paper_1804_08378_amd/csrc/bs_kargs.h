@@ -46,6 +46,7 @@ constexpr int K_MAX_STREAM_EW = 16;
 constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
 constexpr int K_STREAM_U = 2;     // 128-bit vectors per lane in stream_kernel (measured on MI355X: 1 is 3..9 points of HBM peak slower, 4 is 1..3 slower with 16-bit storage)
+constexpr int K_ROWS_OR = 2;     // output rows per lane per iteration of the one-level sliding-window kernels (all their input rows are requested at once)
 constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
 // Elements per lane and row (the lane's column block) of the sliding-window kernels for 16-bit
 // storage: one 128-bit load, as for float32 (4).  Measured on MI355X, 64-bit blocks (twice the
@@ -53,6 +54,12 @@ constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
 constexpr int K_ROWS_VEC16 = 8;
 constexpr int K_ROWS2_VEC16 = 8;
 constexpr int K_ROWS2_VEC32 = 4;  // float32 in the two-level kernel (8, two loads per row, measured 5 % slower: registers)
+// Column block of the sliding-window kernels whose lanes exchange edge columns (whole 128-bit vectors).
+constexpr int K_XROWS_VEC32 = 4, K_XROWS_VEC16 = 8;    // one pooling operation
+constexpr int K_XROWS2_VEC32 = 4, K_XROWS2_VEC16 = 8;  // two pooling operations (float32 with 8: measured 4 .. 9 % slower)
+// Output rows per lane in pool_xrows2_kernel.  Longer chunks recompute less, but the kernel is bound by
+// instruction issue and wants many waves: measured best on 56 x 56 planes.
+constexpr int K_XROWS2_RC32 = 2, K_XROWS2_RC16 = 4;
 constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel (2 measured 1..2 % slower on the VGG stacks)
 constexpr int K_PLANE_WALK_CELLS = 16;  // whole-plane pooling: planes up to this many cells are walked in global
@@ -161,6 +168,9 @@ struct PoolRowsK {
     int32_t cbs;      // 128-bit column blocks per input row = W / vec
     uint32_t total;   // lanes with work = planes * chunks * cbs
     FastDiv div_cbs, div_chunks, div_c;
+    // lane-exchange kernel only (spw == 0: the kernel that loads its edge columns)
+    int32_t spw;      // (plane, chunk) segments of cbs lanes per wave = 64 / cbs
+    uint32_t units;   // segments = planes * chunks
 };
 
 // Two pooling operations in one register sliding-window kernel: pre, pool1, mid, pool2, post.
@@ -179,6 +189,9 @@ struct PoolRows2K {
     int32_t cbs;      // 128-bit column blocks per input row = W / vec
     uint32_t total;   // lanes with work = planes * chunks * cbs
     FastDiv div_cbs, div_chunks, div_c;
+    // lane-exchange kernel only (spw == 0: the kernel that loads its edge columns)
+    int32_t spw;      // (plane, chunk) segments of cbs lanes per wave = 64 / cbs
+    uint32_t units;   // segments = planes * chunks
 };
 
 // Channels-last (N, H, W, C in memory) sequences: element-wise only (pool.kind == 0, the list

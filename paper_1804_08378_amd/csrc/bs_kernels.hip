@@ -641,8 +641,10 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
             k.in_extra = in_extra; k.out_extra = out_extra;
             k.idx = ip[0];
             const bool want_idx = k.idx != nullptr && k.pool2.kind == OP_MAXPOOL;
+            if (k.spw > 0 && !xrows2_launchable(k, dtype, q.grid, q.threads)) return BS_ERR_UNSUPPORTED;
             const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
-                                       : launch_rows2(k, dtype, q.grid, q.threads, stream);
+                                       : (k.spw > 0 ? launch_xrows2(k, dtype, q.grid, q.threads, stream)
+                                                    : launch_rows2(k, dtype, q.grid, q.threads, stream));
             if (ls != BS_OK) return ls;
             break;
         }
@@ -651,8 +653,10 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         k.in_extra = in_extra; k.out_extra = out_extra;
         k.idx = ip[0];
         const bool want_idx = k.idx != nullptr && k.pool.kind == OP_MAXPOOL;
+        if (k.spw > 0 && !xrows_launchable(k, dtype, q.grid, q.threads)) return BS_ERR_UNSUPPORTED;
         const bs_status ls = q.jit ? launch_built(q, want_idx, &k, sizeof k, stream)
-                                   : launch_rows(k, dtype, q.grid, q.threads, stream);
+                                   : (k.spw > 0 ? launch_xrows(k, dtype, q.grid, q.threads, stream)
+                                                : launch_rows(k, dtype, q.grid, q.threads, stream));
         if (ls != BS_OK) return ls;
         break;
     }

@@ -632,11 +632,18 @@ static bool rows_columns_pay(const bs_stack *s, int32_t nc0, int32_t vec)
     return nc0 * 4 <= vec * 7 || !jit_allowed(s) || s->opts.force_variant == BS_VARIANT_POOL_ROWS;
 }
 
+// May the sliding-window kernels whose lanes exchange edge columns serve a plane of width W?  All
+// column blocks of a row must sit in one wave.
+static bool exchange_fits(const bs_stack *s, int32_t W, int32_t vec)
+{
+    return s->opts.lane_exchange >= 0 && W % vec == 0 && W / vec <= 64;
+}
+
 // Two consecutive pooling operations, BatchNorm and ReLU only around them, no index output on
-// the first, in shapes the two-level rows kernel is instantiated for (or can be built for).
+// the first, in shapes one of the two-level rows kernels is instantiated for (or can be built
+// for).  Preferred: the kernel whose lanes exchange edge columns (k.spw > 0 says so).
 static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
 {
-    const int32_t vec = rows2_vec(s->dtype);
     Sequence tmp;
     Sequence &q = fill ? *fill : tmp;
     PoolRows2K k{};
@@ -645,7 +652,7 @@ static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
         const Op &op = s->ops[i];
         if (!op_is_elementwise(op.kind)) {
             if (seen == 0) {
-                if (op.idx_slot >= 0 || op.in_w % vec != 0) return false;
+                if (op.idx_slot >= 0) return false;
                 k.pool1 = make_pool(op, nullptr, q);
                 k.H = op.in_h; k.W = op.in_w; k.H1 = op.out_h; k.W1 = op.out_w;
             } else {
@@ -662,9 +669,24 @@ static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
         }
     }
     if (seen != 2) return false;
-    if (!(dtype_has_tables(s->dtype) && rows2_supported(k)) && !(jit_allowed(s) && rows2_buildable(k, vec))) return false;
-    // every output column must fall under some lane's column block
     const int32_t sws = k.pool1.sw * k.pool2.sw;
+    const bool in_table = dtype_has_tables(s->dtype) && rows2_supported(k);
+    // lanes exchange edge columns: every column of the plane between the pools and every output
+    // column must belong to some lane
+    {
+        const int32_t vec = xrows2_vec(s->dtype);
+        if (exchange_fits(s, k.W, vec) && sws >= 1 && vec % sws == 0 && (in_table || (jit_allowed(s) && xrows2_buildable(k, vec))) &&
+            (int64_t)(k.W / vec) * (vec / k.pool1.sw) >= k.W1 && (int64_t)(k.W / vec) * (vec / sws) >= k.Wo) {
+            k.cbs = k.W / vec;
+            k.spw = 64 / k.cbs;
+            if (fill) fill->rows2 = k;
+            return true;
+        }
+    }
+    const int32_t vec = rows2_vec(s->dtype);
+    if (k.W % vec != 0) return false;
+    if (!in_table && !(jit_allowed(s) && rows2_buildable(k, vec))) return false;
+    // every output column must fall under some lane's column block
     if (vec % sws != 0 || (int64_t)(k.W / vec) * (vec / sws) < k.Wo) return false;
     {
         const int32_t nc1 = (vec / sws - 1) * k.pool2.sw + k.pool2.kw;
@@ -675,12 +697,12 @@ static bool rows2_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
 }
 
 // One pooling operation with overlapping / padded windows, BatchNorm and ReLU only around it,
-// in a shape the rows kernel is instantiated for -- or two such operations (rows2_applicable).
+// in a shape one of the rows kernels is instantiated for -- or two such operations
+// (rows2_applicable).  Preferred: the kernel whose lanes exchange edge columns (k.spw > 0).
 static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
 {
     if (count_pools(s, first_op, n_ops) == 2) return rows2_applicable(s, first_op, n_ops, fill);
     if (count_pools(s, first_op, n_ops) != 1) return false;
-    const int32_t vec = rows_vec(s->dtype);
     Sequence tmp;
     Sequence &q = fill ? *fill : tmp;
     PoolRowsK k{};
@@ -688,7 +710,6 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
     for (int32_t i = first_op; i < first_op + n_ops; ++i) {
         const Op &op = s->ops[i];
         if (!op_is_elementwise(op.kind)) {
-            if (op.in_w % vec != 0 || vec % op.sw != 0 || op.kw - op.sw - op.pw < 0) return false;
             k.pool = make_pool(op, nullptr, q);
             k.H = op.in_h; k.W = op.in_w; k.Ho = op.out_h; k.Wo = op.out_w;
             seen = true;
@@ -700,9 +721,22 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
         }
     }
     if (!seen) return false;
-    if (!(dtype_has_tables(s->dtype) && rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) &&
-        !(jit_allowed(s) && rows_buildable(k.pool, k.pre, k.n_pre, k.post, k.n_post, vec)))
-        return false;
+    if (k.pool.sw < 1 || k.pool.kw - k.pool.sw - k.pool.pw < 0) return false;
+    const bool in_table = dtype_has_tables(s->dtype) && rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post);
+    {
+        const int32_t vec = xrows_vec(s->dtype);
+        if (exchange_fits(s, k.W, vec) && vec % k.pool.sw == 0 &&
+            (in_table || (jit_allowed(s) && xrows_buildable(k.pool, k.pre, k.n_pre, k.post, k.n_post, vec))) &&
+            (int64_t)(k.W / vec) * (vec / k.pool.sw) >= k.Wo) {
+            k.cbs = k.W / vec;
+            k.spw = 64 / k.cbs;
+            if (fill) fill->rows = k;
+            return true;
+        }
+    }
+    const int32_t vec = rows_vec(s->dtype);
+    if (k.W % vec != 0 || vec % k.pool.sw != 0) return false;
+    if (!in_table && !(jit_allowed(s) && rows_buildable(k.pool, k.pre, k.n_pre, k.post, k.n_post, vec))) return false;
     // every output column must fall under some lane's column block
     if ((int64_t)(k.W / vec) * (vec / k.pool.sw) < k.Wo) return false;
     if (!rows_columns_pay(s, vec + k.pool.kw - k.pool.sw, vec)) return false;
@@ -710,26 +744,52 @@ static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, 
     return true;
 }
 
+// Argument block and launch shape of a lane-exchange kernel: spw segments of cbs lanes per wave,
+// whole waves, chunks of rc output rows evened out over the plane.
+template <class K>
+static void plan_exchange(Sequence &q, K &k, int64_t planes, int32_t rc, int32_t multiple)
+{
+    rc = std::max(1, std::min(rc, k.Ho));
+    k.chunks = (k.Ho + rc - 1) / rc;
+    rc = (k.Ho + k.chunks - 1) / k.chunks;
+    k.rc = (rc + multiple - 1) / multiple * multiple;
+    k.chunks = (k.Ho + k.rc - 1) / k.rc;
+    k.units = (uint32_t)(planes * k.chunks);
+    k.total = (uint32_t)(planes * k.chunks * k.cbs);
+    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+    k.div_c = make_fastdiv((uint32_t)k.C);
+    q.threads = 256;
+    const int64_t per_group = (int64_t)k.spw * (q.threads / 64);
+    q.grid = ((int64_t)k.units + per_group - 1) / per_group;
+}
+
 static void plan_rows2(const bs_stack *s, Sequence &q, const bs_plan_options &o)
 {
     PoolRows2K &k = q.rows2;
-    const int32_t vec = rows2_vec(s->dtype);
+    const int32_t vec = k.spw > 0 ? xrows2_vec(s->dtype) : rows2_vec(s->dtype);
     q.vec = vec;
     q.threads = std::min(q.threads, 256);
     k.C = (int32_t)q.in_shape[1];
     const int64_t planes = q.in_shape[0] * q.in_shape[1];
     k.cbs = k.W / vec;
-    // Output rows per lane: a chunk recomputes the level-1 rows and re-reads the input rows it
-    // shares with the chunk above, so chunks are longer than in the one-level kernel.
-    int32_t rc = std::min(K_ROWS2_RC, k.Ho);
-    if (o.tile_rows > 0) rc = std::min(o.tile_rows, k.Ho);
-    k.rc = std::max(1, rc);
-    k.chunks = (k.Ho + k.rc - 1) / k.rc;
-    k.total = (uint32_t)(planes * k.chunks * k.cbs);
-    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
-    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
-    k.div_c = make_fastdiv((uint32_t)k.C);
-    q.grid = ((int64_t)k.total + q.threads - 1) / q.threads;
+    if (k.spw > 0) {
+        // Output rows per lane: a chunk recomputes the level-1 rows and re-reads the input rows
+        // it shares with the chunk above.
+        plan_exchange(q, k, planes, o.tile_rows > 0 ? o.tile_rows : (s->dtype == BS_F32 ? K_XROWS2_RC32 : K_XROWS2_RC16), 1);
+    } else {
+        // Output rows per lane: a chunk recomputes the level-1 rows and re-reads the input rows it
+        // shares with the chunk above, so chunks are longer than in the one-level kernel.
+        int32_t rc = std::min(K_ROWS2_RC, k.Ho);
+        if (o.tile_rows > 0) rc = std::min(o.tile_rows, k.Ho);
+        k.rc = std::max(1, rc);
+        k.chunks = (k.Ho + k.rc - 1) / k.rc;
+        k.total = (uint32_t)(planes * k.chunks * k.cbs);
+        k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+        k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+        k.div_c = make_fastdiv((uint32_t)k.C);
+        q.grid = ((int64_t)k.total + q.threads - 1) / q.threads;
+    }
     q.lds_bytes = 0;
     q.tile_rows = k.rc;
     q.tile_cols = k.Wo;
@@ -759,7 +819,7 @@ static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, 
         return;
     }
     PoolRowsK &k = q.rows;
-    const int32_t vec = rows_vec(s->dtype);
+    const int32_t vec = k.spw > 0 ? xrows_vec(s->dtype) : rows_vec(s->dtype);
     q.vec = vec;
     q.threads = std::min(q.threads, 256);
     k.C = (int32_t)q.in_shape[1];
@@ -773,13 +833,17 @@ static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, 
     int32_t rc = std::min(2, k.Ho);
     (void)lim;
     if (o.tile_rows > 0) rc = std::min(o.tile_rows, k.Ho);
-    k.rc = std::max(1, rc);
-    k.chunks = (k.Ho + k.rc - 1) / k.rc;
-    k.total = (uint32_t)(planes * k.chunks * k.cbs);
-    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
-    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
-    k.div_c = make_fastdiv((uint32_t)k.C);
-    q.grid = ((int64_t)k.total + q.threads - 1) / q.threads;
+    if (k.spw > 0) {
+        plan_exchange(q, k, planes, rc, K_ROWS_OR);  // the kernel produces K_ROWS_OR output rows per iteration
+    } else {
+        k.rc = std::max(1, rc);
+        k.chunks = (k.Ho + k.rc - 1) / k.rc;
+        k.total = (uint32_t)(planes * k.chunks * k.cbs);
+        k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+        k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+        k.div_c = make_fastdiv((uint32_t)k.C);
+        q.grid = ((int64_t)k.total + q.threads - 1) / q.threads;
+    }
     q.lds_bytes = 0;
     q.tile_rows = k.rc;
     q.tile_cols = k.Wo;
@@ -1029,11 +1093,14 @@ static bool audit_lds(const Sequence &q)
 static const char *jit_names(const bs_stack *s, const Sequence &q, std::string (&expr)[2])
 {
     for (int w = 0; w < 2; ++w) {
-        if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) expr[w] = rows2_expr(q.rows2, s->dtype, w != 0);
-        else if (q.variant == BS_VARIANT_POOL_ROWS) expr[w] = rows_expr(q.rows, s->dtype, w != 0);
+        if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2)
+            expr[w] = q.rows2.spw > 0 ? xrows2_expr(q.rows2, s->dtype, w != 0) : rows2_expr(q.rows2, s->dtype, w != 0);
+        else if (q.variant == BS_VARIANT_POOL_ROWS)
+            expr[w] = q.rows.spw > 0 ? xrows_expr(q.rows, s->dtype, w != 0) : rows_expr(q.rows, s->dtype, w != 0);
         else expr[w] = lds_expr(q.lds, s->dtype, w != 0);
     }
-    return q.variant == BS_VARIANT_POOL_ROWS ? "bs_rows_device.h" : "bs_lds_device.h";
+    if (q.variant != BS_VARIANT_POOL_ROWS) return "bs_lds_device.h";
+    return (q.n_levels == 2 ? q.rows2.spw : q.rows.spw) > 0 ? "bs_xrows_device.h" : "bs_rows_device.h";
 }
 
 // Decide whether the sequence runs a pre-compiled kernel or a run-time build, and (unless
@@ -1046,8 +1113,12 @@ static bs_status prepare_jit(bs_stack *s, Sequence &q, bool host_only)
     const bool tables = dtype_has_tables(s->dtype);
     // the sliding-window kernels (compiled in or built here) are instantiated for one column-block
     // width per storage type; a plan made for another width must never reach them
-    if (q.variant == BS_VARIANT_POOL_ROWS && q.vec != (q.n_levels == 2 ? rows2_vec(s->dtype) : rows_vec(s->dtype)))
-        return BS_ERR_UNSUPPORTED;
+    if (q.variant == BS_VARIANT_POOL_ROWS) {
+        const bool two = q.n_levels == 2, exchange = (two ? q.rows2.spw : q.rows.spw) > 0;
+        const int32_t vec = exchange ? (two ? xrows2_vec(s->dtype) : xrows_vec(s->dtype))
+                                     : (two ? rows2_vec(s->dtype) : rows_vec(s->dtype));
+        if (q.vec != vec) return BS_ERR_UNSUPPORTED;
+    }
     if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2) {
         if (tables && rows2_supported(q.rows2)) return BS_OK;
     } else if (q.variant == BS_VARIANT_POOL_ROWS) {
@@ -1219,6 +1290,7 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (o.max_lds_bytes > 64 * 1024) return BS_ERR_PARAM;
     if (o.jit < -1 || o.jit > 1) return BS_ERR_PARAM;
     if (o.layout != BS_LAYOUT_NCHW && o.layout != BS_LAYOUT_NHWC) return BS_ERR_PARAM;
+    if (o.lane_exchange < -1 || o.lane_exchange > 0) return BS_ERR_PARAM;
     // channels-last plans have their own two kernels: nothing to force, no tiles to set
     if (o.layout == BS_LAYOUT_NHWC && o.force_variant != BS_VARIANT_AUTO) return BS_ERR_PARAM;
 

@@ -3,7 +3,7 @@
 #include <string>
 #include <type_traits>
 
-#include "bs_rows_device.h"
+#include "bs_rows_tables.h"
 #include "bs_internal.h"
 
 namespace bs {
@@ -11,23 +11,6 @@ namespace bs {
 // =============================================================================
 // Signature table, applicability test and launcher.
 // =============================================================================
-// visit every instantiated signature; F(spec tag, pre code, post code) returns true to stop
-template <class F>
-static bool rows_for_each_signature(F &&f)
-{
-    return f(RMax3s2p1{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RMax3s2p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RMax3s2p0{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RMax3s2p0{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RMax3s2p0{}, std::integral_constant<int, RW_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RMax3s2p1{}, std::integral_constant<int, RW_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RMax3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_BN_RELU>{}) ||
-           f(RMax3s1p1{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RMax3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RAvg3s1p1{}, std::integral_constant<int, RW_BN_RELU>{}, std::integral_constant<int, RW_NONE>{}) ||
-           f(RAvg3s1p1{}, std::integral_constant<int, RW_NONE>{}, std::integral_constant<int, RW_NONE>{});
-}
-
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post)
 {
     const int cp = rows_ew_code(pre, n_pre), cq = rows_ew_code(post, n_post);

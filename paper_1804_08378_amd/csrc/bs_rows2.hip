@@ -3,7 +3,7 @@
 #include <string>
 #include <type_traits>
 
-#include "bs_rows_device.h"
+#include "bs_rows_tables.h"
 #include "bs_internal.h"
 
 namespace bs {
@@ -11,18 +11,6 @@ namespace bs {
 // =============================================================================
 // Signature table, applicability test and launcher.
 // =============================================================================
-template <int V>
-using IC = std::integral_constant<int, V>;
-
-// visit every instantiated signature; F(pool 1, pool 2, code 0, code 1, code 2) returns true to stop
-template <class F>
-static bool rows2_for_each_signature(F &&f)
-{
-    return f(RAvg3s1p1{}, RMax3s2p1{}, IC<RW_BN_RELU>{}, IC<RW_NONE>{}, IC<RW_BN_RELU>{}) ||
-           f(RMax3s1p1{}, RMax3s1p1{}, IC<RW_NONE>{}, IC<RW_BN_RELU>{}, IC<RW_BN_RELU>{}) ||
-           f(RMax3s1p1{}, RAvg3s1p1{}, IC<RW_NONE>{}, IC<RW_BN_RELU>{}, IC<RW_NONE>{});
-}
-
 bool rows2_supported(const PoolRows2K &k)
 {
     const int c0 = rows_ew_code(k.pre, k.n_pre), c1 = rows_ew_code(k.mid, k.n_mid), c2 = rows_ew_code(k.post, k.n_post);

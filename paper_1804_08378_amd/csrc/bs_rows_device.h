@@ -11,7 +11,6 @@ struct RowsSpec {
 };
 
 // element-wise list codes (base K_EW_BASE digits, first operation lowest): see rows_ew_code()
-constexpr int K_ROWS_OR = 2;  // output rows per lane per iteration (all their input rows are requested at once)
 constexpr int RW_NONE = 0;
 constexpr int RW_RELU = OP_RELU;
 constexpr int RW_BN_RELU = OP_BN + K_EW_BASE * OP_RELU;

@@ -280,16 +280,25 @@ def _rows_stacks(c):
     }
 
 
-@pytest.mark.parametrize("shape", [(2, 3, 12, 16), (1, 2, 9, 8), (3, 5, 33, 24), (1, 4, 64, 64), (1, 1, 3, 8)])
+# rows of 8 ... 64 column blocks of four float32 values, one more than a wave holds (the lanes
+# of such a plane load their edge columns instead of exchanging them), a wave with 31 idle lanes
+ROWS_SHAPES = [(2, 3, 12, 16), (1, 2, 9, 8), (3, 5, 33, 24), (1, 4, 64, 64), (1, 1, 3, 8), (2, 3, 57, 56),
+               (1, 2, 10, 256), (1, 1, 7, 264), (2, 3, 20, 136)]
+
+
+@pytest.mark.parametrize("shape", ROWS_SHAPES)
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_pool_rows_kernel(shape, dtype):
     """Single pooling step with overlapping / padded windows through the register-sliding
-    rows kernel, for several chunk lengths (1 row per lane, ragged, whole plane)."""
+    rows kernels -- lanes exchanging their edge columns, and lanes loading them -- for several
+    chunk lengths (1 row per lane, ragged, whole plane)."""
     for name, layers in _rows_stacks(shape[1]).items():
         x = wl.activation(shape, 70, dtype)
         for rc in (0, 1, 3, 1000):
-            info = check(layers, x, [], dtype, f"rows/{name}{shape}/rc{rc}", tile_rows=rc)
-            assert info["sequences"][0]["variant_name"] == "pool_rows", name
+            for exchange in (0, -1):
+                info = check(layers, x, [], dtype, f"rows/{name}{shape}/rc{rc}/x{exchange}", tile_rows=rc,
+                             lane_exchange=exchange)
+                assert info["sequences"][0]["variant_name"] == "pool_rows", name
         # the same stack through the LDS kernels agrees as well
         info = check(layers, x, [], dtype, f"rows/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
         assert info["sequences"][0]["variant_name"] == "lds_tile"
@@ -307,20 +316,20 @@ def _rows2_stacks(c):
     }
 
 
-@pytest.mark.parametrize("shape", [(2, 3, 12, 16), (1, 2, 9, 8), (3, 5, 33, 24), (1, 4, 64, 64), (1, 1, 3, 8),
-                                   (1, 2, 1, 8), (2, 2, 2, 16)])
+@pytest.mark.parametrize("shape", ROWS_SHAPES + [(1, 2, 1, 8), (2, 2, 2, 16)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_pool_rows2_kernel(shape, dtype):
-    """Two pooling steps in one sequence through the two-level register-sliding kernel, for
-    several chunk lengths (1 row per lane, ragged, whole plane), and the same stacks through
-    the LDS kernels."""
+    """Two pooling steps in one sequence through the two-level register-sliding kernels (lanes
+    exchanging their edge columns, and lanes recomputing them), for several chunk lengths (1 row
+    per lane, ragged, whole plane), and the same stacks through the LDS kernels."""
     for name, layers in _rows2_stacks(shape[1]).items():
         x = wl.activation(shape, 71, dtype)
         for rc in (0, 1, 3, 1000):
-            info = check(layers, x, [], dtype, f"rows2/{name}{shape}/rc{rc}", tile_rows=rc,
-                         force_variant=bs.BS_VARIANT_POOL_ROWS)
-            assert info["n_sequences"] == 1, name
-            assert info["sequences"][0]["variant_name"] == "pool_rows", name
+            for exchange in (0, -1):
+                info = check(layers, x, [], dtype, f"rows2/{name}{shape}/rc{rc}/x{exchange}", tile_rows=rc,
+                             force_variant=bs.BS_VARIANT_POOL_ROWS, lane_exchange=exchange)
+                assert info["n_sequences"] == 1, name
+                assert info["sequences"][0]["variant_name"] == "pool_rows", name
         info = check(layers, x, [], dtype, f"rows2/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
         assert [q["variant_name"] for q in info["sequences"]] == ["lds_tile"] * info["n_sequences"]
 

@@ -45,17 +45,19 @@ def test_run_time_builds_compile_without_a_device():
     plan, and those builds compile for gfx950 on a machine without a GPU."""
     cases = [
         ([wl.bn_params(4, 0), wl.relu(), wl.maxpool((3, 2), (1, 2), (1, 0), True)], (2, 4, 32, 32), ["pool_rows"], 2),
-        # 5x5 windows: a lane of the rows kernel would compute 8 columns for 4 owned (float32) or
-        # 12 for 8 (16-bit types); LDS shares them between lanes and wins in the first case
-        ([wl.maxpool(5, 1, 2, True), wl.bn_params(4, 0), wl.relu()], (2, 4, 32, 32),
-         {"f32": ["lds_tile"], "bf16": ["pool_rows"], "f16": ["pool_rows"]}, 2),
+        # 5x5 windows: lanes that exchange their edge columns serve them in registers ...
+        ([wl.maxpool(5, 1, 2, True), wl.bn_params(4, 0), wl.relu()], (2, 4, 32, 32), ["pool_rows"], 2),
         ([wl.maxpool(3, 2, 1), wl.bn_params(4, 1), wl.relu(), wl.avgpool(2, 2), wl.maxpool(3, 1, 1)],
          (2, 4, 64, 64), ["lds_tile"], 1),
         ([wl.bn_params(4, 2), wl.add(), wl.relu(), wl.maxpool(3, 2, 1)], (1, 4, 30, 30), ["lds_tile"], 1),
     ]
+    # ... without the exchange a lane of the rows kernel would compute 8 columns for 4 owned (float32)
+    # or 12 for 8 (16-bit types); LDS shares them between lanes and wins in the first case
+    cases.append(([wl.maxpool(5, 1, 2, True), wl.bn_params(4, 0), wl.relu()], (2, 4, 32, 32),
+                  {"f32": ["lds_tile"], "bf16": ["pool_rows"], "f16": ["pool_rows"]}, 2, {"lane_exchange": -1}))
     for dt in ("f32", "bf16", "f16"):
-        for layers, shape, variants, n_kernels in cases:
-            st = bs.Stack(layers, shape, dt).plan(host_only=1, num_cus=256)
+        for layers, shape, variants, n_kernels, *more in cases:
+            st = bs.Stack(layers, shape, dt).plan(host_only=1, num_cus=256, **(more[0] if more else {}))
             info = st.info()
             want = variants[dt] if isinstance(variants, dict) else variants
             assert [q["variant_name"] for q in info["sequences"]] == want
