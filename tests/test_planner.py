@@ -107,8 +107,9 @@ def test_baseline_configs_are_one_fused_sequence(name, steps, variant):
         assert q["lds_bytes"] <= 64 * 1024
         assert q["grid"] >= 1
         if name == "halo_stress":
-            # four output rows per lane: 2*4 + 3 input rows of every 8 are loaded
-            assert 1.0 <= q["redundancy"] < 1.45
+            # rc output rows per lane (2 for float32, 4 for the 16-bit types): 2 rc + 3 input rows of every
+            # 2 rc are loaded; only rows shared with the chunk above are read twice, never columns
+            assert 1.0 <= q["redundancy"] < (1.75 if dt == "f32" else 1.45)
             lds = plan(layers, shape, dt, num_cus=256, force_variant=bs.BS_VARIANT_LDS_TILE)["sequences"]
             assert len(lds) == 1 and lds[0]["variant_name"] == "lds_tile" and 1.0 <= lds[0]["redundancy"] < 1.1
     if name == "halo_stress":
