@@ -11,8 +11,11 @@ every launch reads a buffer set that has not been touched for >= 1 GB of traffic
 Prints ONE JSON line on stdout: whole-step effective GB/s (algorithmic bytes /
 wall time), the roofline entry of the dominant kernel (the 64x224x224 stack),
 the speed-up over the layer-by-layer HIP plan, and the CPU oracle timed on a
-bounded sample.  `--all` adds a per-configuration table (stderr) for every
-benchmark configuration and dtype.
+bounded sample.  The line also carries `all_configs`: every benchmark configuration and
+storage type timed back to back over rotating buffers (kernel family, microseconds, GB/s,
+fraction of the HBM peak).  `--all` adds the long per-configuration table (stderr) with the
+layer-by-layer plan and single-launch event timings; `--batch-fit` times the pooling
+configurations at several batch sizes and fits time = fixed cost + bytes / rate.
 """
 from __future__ import annotations
 
@@ -132,6 +135,81 @@ def time_back_to_back(sb, which, launches, hot=False):
     return a.elapsed_time(b) / launches
 
 
+def all_configs_summary(launches=60):
+    """Every benchmark configuration and storage type, index outputs off: `launches` launches of
+    the fused plan back to back over rotating buffer sets between one HIP event pair."""
+    import torch
+    from paper_1804_08378_amd import workloads as wl
+
+    rows = []
+    for name in wl.CONFIG_NAMES:
+        for dt in wl.build(name)[2]:
+            sb = StackBench(name, dt)
+            us = time_back_to_back(sb, "fused", launches) * 1e3
+            g = sb.bytes / us * 1e-3
+            rows.append({"config": name, "dtype": dt, "kernels": [q["variant_name"] for q in sb.info["sequences"]],
+                         "work_groups": [q["grid"] for q in sb.info["sequences"]], "MB": round(sb.bytes / 1e6, 2),
+                         "us": round(us, 2), "GBps": round(g, 1), "frac": round(g / HBM_PEAK_GBPS, 4)})
+            log(f"all_configs {name:<16}{dt:<6}{'+'.join(rows[-1]['kernels']):<14}{rows[-1]['MB']:>8.1f} MB"
+                f"{us:>8.1f} us{g:>8.0f} GB/s{100 * g / HBM_PEAK_GBPS:>6.1f} %")
+            del sb
+            torch.cuda.empty_cache()
+    return rows
+
+
+def batch_fit(configs=(("vgg_c", "f32"), ("densenet_trans", "f32"), ("resnet_stem", "f32"), ("resnet_stem", "bf16"),
+                       ("halo_stress", "f32"), ("halo_stress", "bf16")), factors=(0.25, 0.5, 1, 2, 4), launches=60):
+    """Time = fixed cost per launch + bytes / streaming rate?  Each configuration at several
+    multiples of its batch size (same planes, same kernel), least-squares line through
+    (bytes, microseconds).  The intercept is what a launch costs however little it moves
+    (dispatch, the first memory round trip, the last waves draining); the slope is the rate the
+    kernel streams at once the chip is full."""
+    import torch
+    from paper_1804_08378_amd import brainslug as bs
+    from paper_1804_08378_amd import workloads as wl
+
+    rows = []
+    for name, dt in configs:
+        layers, shape, _ = wl.build(name)
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dt]
+        pts = []
+        for f in factors:
+            n = max(1, int(round(shape[0] * f)))
+            shp = (n,) + tuple(shape[1:])
+            byts = wl.algorithmic_bytes(layers, shp, dt, False)
+            sets = max(2, min(32, (1 << 30) // byts + 1))
+            xs = [torch.randn(shp, device="cuda").to(tdt) for _ in range(sets)]
+            st = bs.Stack(layers, shp, dt).plan()
+            outs = [st.alloc_outputs("cuda", False)[0] for _ in range(sets)]
+            for i in range(3):
+                st.run(xs[i % sets], out=outs[i % sets], indices=[])
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for i in range(launches):
+                st.run(xs[i % sets], out=outs[i % sets], indices=[])
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) / launches * 1e3
+            pts.append((byts, us, n))
+            st.close()
+            del xs, outs
+            torch.cuda.empty_cache()
+        # least squares through the three largest sizes (the smallest do not fill the chip)
+        use = pts[-3:]
+        mx = sum(p[0] for p in use) / len(use)
+        my = sum(p[1] for p in use) / len(use)
+        slope = sum((p[0] - mx) * (p[1] - my) for p in use) / sum((p[0] - mx) ** 2 for p in use)
+        icpt = my - slope * mx
+        row = {"config": name, "dtype": dt, "points": [{"batch": n, "MB": round(b / 1e6, 1), "us": round(u, 2),
+                                                         "GBps": round(b / u * 1e-3, 1)} for b, u, n in pts],
+               "fixed_us": round(icpt, 2), "streaming_GBps": round(1e-3 / slope, 1)}
+        rows.append(row)
+        log(f"batch_fit {name:<16}{dt:<6} fixed {icpt:5.1f} us, streaming {1e-3 / slope:6.0f} GB/s   " +
+            "  ".join(f"n={n}: {u:.1f} us" for _, u, n in pts))
+    return rows
+
+
 def cpu_baseline(names, dtype, batch, passes):
     """Time the breadth-first CPU oracle, as it stands, on the same stacks: `passes` passes over
     the workload at `batch` images with all host threads, plus one single-thread pass."""
@@ -160,231 +238,6 @@ def cpu_baseline(names, dtype, batch, passes):
             "sample": f"stacks {'+'.join(names)} at batch {batch} (the full workload), {passes} passes with "
                       f"{threads} OpenMP threads (~{t_all * passes * threads:.0f} core-seconds) and one "
                       "single-thread pass; same algorithmic-bytes metric"}
-
-
-def frontend_stacks(names=("vgg_a", "vgg_b", "vgg_c"), batch=32, reps=50):
-    """The optimizable layers of the VGG-16-BN feature extractor as torch modules (BatchNorm2d,
-    ReLU, MaxPool2d in eval mode), run by PyTorch's own kernels and, after `frontend.optimize`,
-    by this library (Section 5.3 reports the speed-up of the optimizable layers alone).  Module
-    calls back to back over rotating inputs, HIP events around the loop: the figures include
-    Python and allocator overhead of both sides."""
-    import torch
-    from torch import nn
-    from paper_1804_08378_amd import frontend as fe
-    from paper_1804_08378_amd import workloads as wl
-
-    rows, tot_ref, tot_opt = [], 0.0, 0.0
-    log(f"{'stack':<8}{'torch eager us':>16}{'optimized us':>14}{'speed-up':>10}")
-    for name in names:
-        layers, x, _ = wl.inputs_for(name, 0, "f32", batch=batch, indices=False)
-        c = x.shape[1]
-        bn = nn.BatchNorm2d(c, eps=float(layers[0]["eps"]))
-        with torch.no_grad():
-            bn.weight.copy_(torch.from_numpy(layers[0]["gamma"]))
-            bn.bias.copy_(torch.from_numpy(layers[0]["beta"]))
-            bn.running_mean.copy_(torch.from_numpy(layers[0]["mean"]))
-            bn.running_var.copy_(torch.from_numpy(layers[0]["var"]))
-        ref = nn.Sequential(bn, nn.ReLU(), nn.MaxPool2d(2, 2)).cuda().eval()
-        import copy
-        opt = fe.optimize(copy.deepcopy(ref))
-        xs = [torch.from_numpy(x).cuda()]
-        xs += [xs[0].clone() for _ in range(3)]
-        t = {}
-        with torch.no_grad():
-            same = torch.equal(ref(xs[0]), opt(xs[0])) or float((ref(xs[0]) - opt(xs[0])).abs().max())
-            for key, mod in (("ref", ref), ("opt", opt)):
-                for i in range(3):
-                    mod(xs[i])
-                torch.cuda.synchronize()
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                for i in range(reps):
-                    mod(xs[i % 4])
-                b.record()
-                torch.cuda.synchronize()
-                t[key] = a.elapsed_time(b) / reps * 1e3
-        rows.append({"stack": name, "torch_eager_us": round(t["ref"], 1), "optimized_us": round(t["opt"], 1),
-                     "speedup": round(t["ref"] / t["opt"], 2), "max_abs_diff_vs_torch": 0.0 if same is True else same})
-        tot_ref += t["ref"]
-        tot_opt += t["opt"]
-        log(f"{name:<8}{t['ref']:>16.1f}{t['opt']:>14.1f}{t['ref'] / t['opt']:>10.2f}")
-        for st in opt.optimized_stacks:
-            st.close()
-        del xs, ref, opt
-    return {"what": "BatchNorm2d -> ReLU -> MaxPool2d(2,2) torch modules, fp32, batch %d" % batch, "rows": rows,
-            "optimizable_layers_speedup": round(tot_ref / tot_opt, 2)}
-
-
-def frontend_network(batch=32, reps=10,
-                     names=("alexnet", "squeezenet1.1", "vgg16", "vgg16_bn", "resnet18", "resnet50", "densenet121",
-                            "inception_v3"),
-                     dtypes=("float32", "float16"), channels_last=False):
-    """Whole networks of the families Sections 5.2-5.4 evaluate (architectures written from their
-    published descriptions in `paper_1804_08378_amd/zoo.py`, hand-written forward methods, random
-    weights, 3 x 224 x 224 inputs, 3 x 299 x 299 for Inception), forward pass by PyTorch eager and after
-    `frontend.optimize_graph`: convolutions and fully connected layers stay in PyTorch on both
-    sides, every chain of BatchNorm / ReLU / Add / pooling operations becomes one stack call.
-    `stacks` / `optimizable` are what the paper's detail table calls Stacks / Opt."""
-    import torch
-    from paper_1804_08378_amd import frontend as fe
-    from paper_1804_08378_amd import zoo
-
-    make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "vgg11_bn": lambda: zoo.vgg_bn(11), "vgg16": lambda: zoo.vgg(16),
-            "resnet18": lambda: zoo.resnet(18), "resnet34": lambda: zoo.resnet(34), "resnet50": lambda: zoo.resnet(50),
-            "resnet101": lambda: zoo.resnet(101), "densenet121": lambda: zoo.densenet(121),
-            "alexnet": lambda: zoo.alexnet(), "squeezenet1.0": lambda: zoo.squeezenet("1.0"),
-            "squeezenet1.1": lambda: zoo.squeezenet("1.1"), "inception_v3": lambda: zoo.inception_v3()}
-    rows = []
-    log(f"{'network':<14}{'dtype':<9}{'stacks':>7}{'opt.':>6}{'torch eager ms':>16}{'optimized ms':>14}{'speed-up %':>12}"
-        f"{'graph torch':>12}{'graph opt.':>12}{'speed-up %':>12}")
-    for name in names:
-        for dname in dtypes:
-            dtype = getattr(torch, dname)
-            torch.manual_seed(0)
-            ref = zoo.randomize_batchnorm(make[name]()).cuda().eval().to(dtype)
-            # frozen BatchNorm layers: running statistics (eval mode) and no gradient for their affine
-            # parameters either, on both sides (a rewritten model has them folded into its stacks)
-            for m in ref.modules():
-                if isinstance(m, torch.nn.BatchNorm2d):
-                    m.weight.requires_grad_(False)
-                    m.bias.requires_grad_(False)
-            size = 299 if name.startswith("inception") else 224
-            xs = [torch.randn(batch, 3, size, size, device="cuda").to(dtype) for _ in range(2)]
-            if channels_last:
-                ref = ref.to(memory_format=torch.channels_last)
-                xs = [x.contiguous(memory_format=torch.channels_last) for x in xs]
-            opt = fe.optimize_graph(ref)
-            t = {}
-            with torch.no_grad():
-                a, b = ref(xs[0]).float(), opt(xs[0]).float()
-                diff = float((a - b).abs().max() / a.abs().max().clamp_min(1e-30))
-                for key, mod in (("ref", ref), ("opt", opt)):
-                    for i in range(3):
-                        mod(xs[i % 2])
-                    torch.cuda.synchronize()
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for i in range(reps):
-                        mod(xs[i % 2])
-                    e1.record()
-                    torch.cuda.synchronize()
-                    t[key] = e0.elapsed_time(e1) / reps
-            # the same two models captured in HIP graphs (torch.cuda.CUDAGraph): no launch overhead
-            # on either side.  Every replay is checked against the eager result, with eager work
-            # between the replays (convolutions are not bit-reproducible from run to run, so the
-            # check is a tolerance); a model whose replays disagree is reported as None.
-            tg = {}
-            # what `frontend.capture` records: the model rewritten with the settings that pay in a graph
-            opt_graph = fe.optimize_graph(ref, lone_activations=True, share_concat_buffers="always")
-            for key, mod in (("ref", ref), ("opt", opt_graph)):
-                with torch.no_grad():
-                    want = mod(xs[0]).float()
-                    side = torch.cuda.Stream()
-                    side.wait_stream(torch.cuda.current_stream())
-                    with torch.cuda.stream(side):
-                        for _ in range(2):
-                            mod(xs[0])
-                    torch.cuda.current_stream().wait_stream(side)
-                    torch.cuda.synchronize()
-                    graph = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(graph):
-                        y = mod(xs[0])
-                    good = True
-                    for _ in range(3):
-                        graph.replay()
-                        torch.cuda.synchronize()
-                        good = good and float((y.float() - want).abs().max() / want.abs().max().clamp_min(1e-30)) < 2e-3
-                        mod(xs[1])  # eager work between the replays
-                        torch.cuda.synchronize()
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    for _ in range(reps):
-                        graph.replay()
-                    e1.record()
-                    torch.cuda.synchronize()
-                    tg[key] = e0.elapsed_time(e1) / reps if good else None
-                    del graph, y
-            n_opt = sum(len(st.replaced) for st in opt.optimized_stacks)
-            both = tg["ref"] is not None and tg["opt"] is not None
-            rows.append({"network": name, "dtype": dname, "stacks": len(opt.optimized_stacks), "optimizable": n_opt,
-                         "torch_eager_ms": round(t["ref"], 3), "optimized_ms": round(t["opt"], 3),
-                         "speedup_pct": round(100 * (t["ref"] / t["opt"] - 1), 1), "max_rel_diff_vs_torch": diff,
-                         "graph_torch_ms": tg["ref"] and round(tg["ref"], 3), "graph_optimized_ms": tg["opt"] and round(tg["opt"], 3),
-                         "graph_speedup_pct": round(100 * (tg["ref"] / tg["opt"] - 1), 1) if both else None})
-            log(f"{name:<14}{dname:<9}{len(opt.optimized_stacks):>7}{n_opt:>6}{t['ref']:>16.3f}{t['opt']:>14.3f}"
-                f"{100 * (t['ref'] / t['opt'] - 1):>12.1f}" +
-                (f"{tg['ref']:>12.3f}{tg['opt']:>12.3f}{100 * (tg['ref'] / tg['opt'] - 1):>12.1f}" if both else "   graph replay differs"))
-            for st in opt.optimized_stacks + opt_graph.optimized_stacks:
-                st.close()
-            del ref, opt, opt_graph, xs
-            torch.cuda.empty_cache()
-    return {"what": "whole forward pass, batch %d, 3x224x224, %s, PyTorch eager vs optimize_graph"
-                    % (batch, "channels_last" if channels_last else "NCHW"), "rows": rows}
-
-
-def frontend_training(batch=32, reps=8, names=("vgg16_bn", "resnet18", "resnet50", "densenet121", "inception_v3"),
-                      dtypes=("float32", "float16"), channels_last=False):
-    """Fine-tuning step with frozen BatchNorm layers (eval mode, autograd on: the paper's outlook,
-    Section 7): forward pass, a scalar loss, backward pass to every convolution and linear weight.
-    PyTorch eager against the model rewritten by `optimize_graph`, whose stacks are single autograd
-    nodes that keep only their operands and recompute in `bs_stack_backward`.  Reports the time of a
-    step and the peak of allocated device memory during it."""
-    import torch
-    from paper_1804_08378_amd import frontend as fe
-    from paper_1804_08378_amd import zoo
-
-    make = {"vgg16_bn": lambda: zoo.vgg_bn(16), "resnet18": lambda: zoo.resnet(18), "resnet50": lambda: zoo.resnet(50),
-            "densenet121": lambda: zoo.densenet(121), "inception_v3": lambda: zoo.inception_v3()}
-    rows = []
-    log("fine-tuning step (forward + backward, frozen BatchNorm), batch %d%s" % (batch, ", channels_last" if channels_last else ""))
-    log(f"{'network':<14}{'dtype':<9}{'torch ms':>10}{'optimized ms':>14}{'speed-up %':>12}{'torch peak MB':>15}{'opt. peak MB':>14}"
-        f"{'memory %':>10}")
-    for name in names:
-        for dname in dtypes:
-            dtype = getattr(torch, dname)
-            torch.manual_seed(0)
-            ref = zoo.randomize_batchnorm(make[name]()).cuda().eval().to(dtype)
-            size = 299 if name.startswith("inception") else 224
-            xs = [torch.randn(batch, 3, size, size, device="cuda").to(dtype) for _ in range(2)]
-            if channels_last:
-                ref = ref.to(memory_format=torch.channels_last)
-                xs = [x.contiguous(memory_format=torch.channels_last) for x in xs]
-            opt = fe.optimize_graph(ref)  # shares the parameters with `ref`
-
-            def step(mod, x):
-                for p in mod.parameters():
-                    p.grad = None
-                loss = mod(x).float().square().mean()
-                loss.backward()
-
-            t, mem = {}, {}
-            for key, mod in (("ref", ref), ("opt", opt)):
-                for i in range(2):
-                    step(mod, xs[i % 2])
-                torch.cuda.synchronize()
-                base = torch.cuda.memory_allocated()
-                torch.cuda.reset_peak_memory_stats()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in range(reps):
-                    step(mod, xs[i % 2])
-                e1.record()
-                torch.cuda.synchronize()
-                t[key] = e0.elapsed_time(e1) / reps
-                mem[key] = (torch.cuda.max_memory_allocated() - base) / 1e6
-                for p in mod.parameters():
-                    p.grad = None
-            rows.append({"network": name, "dtype": dname, "torch_ms": round(t["ref"], 3), "optimized_ms": round(t["opt"], 3),
-                         "speedup_pct": round(100 * (t["ref"] / t["opt"] - 1), 1), "torch_peak_MB": round(mem["ref"], 1),
-                         "optimized_peak_MB": round(mem["opt"], 1), "memory_pct": round(100 * mem["opt"] / mem["ref"], 1)})
-            log(f"{name:<14}{dname:<9}{t['ref']:>10.3f}{t['opt']:>14.3f}{100 * (t['ref'] / t['opt'] - 1):>12.1f}"
-                f"{mem['ref']:>15.1f}{mem['opt']:>14.1f}{100 * mem['opt'] / mem['ref']:>10.1f}")
-            for st in opt.optimized_stacks:
-                st.close()
-            del ref, opt, xs
-            torch.cuda.empty_cache()
-    return {"what": "fine-tuning step (forward + backward, frozen BatchNorm), batch %d, %s"
-                    % (batch, "channels_last" if channels_last else "NCHW"), "rows": rows}
 
 
 def backward_configs(steps=30, warmup=3, min_rotation_bytes=1 << 30, channels_last=False):
@@ -598,17 +451,14 @@ def main():
     ap.add_argument("--streams", action="store_true",
                     help="enqueue the three independent stacks of a step on one HIP stream each (default priority) "
                          "instead of all on one stream: kernels then overlap at their edges")
-    ap.add_argument("--networks", action="store_true",
-                    help="also time whole VGG / ResNet / DenseNet forward passes: PyTorch eager against "
-                         "frontend.optimize_graph()")
-    ap.add_argument("--batch-scaling", action="store_true",
-                    help="also time three whole networks at batch sizes 1 .. 128 (float32, NCHW)")
     ap.add_argument("--backward", action="store_true",
                     help="also time the backward pass of every benchmark configuration against the framework's autograd (stderr)")
     ap.add_argument("--nhwc", action="store_true",
                     help="also time every configuration with channels-last (NHWC) tensors and plans")
-    ap.add_argument("--frontend", action="store_true",
-                    help="also time the VGG stacks as torch modules: PyTorch eager against frontend.optimize()")
+    ap.add_argument("--no-all-configs", action="store_true", help="leave the all_configs summary out of the JSON line")
+    ap.add_argument("--batch-fit", action="store_true",
+                    help="also time the pooling configurations at 1/4 .. 4 times their batch size and fit "
+                         "time = fixed cost + bytes / rate")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
                     help="counter probe for rocprofv3 --pmc: N launches of a plain copy of known size, "
                          "then N launches of each VGG stack; no timing, no JSON")
@@ -660,7 +510,8 @@ def main():
         ms_lbl, per_lbl, _ = time_steps(stacks, "lbl", max(10, args.steps // 4), max(2, args.warmup // 2), streams)
     value = step_bytes / (ms * 1e-3) / 1e9
     dom = stacks[0]
-    dom_ms = time_back_to_back(dom, "fused", max(20, args.steps // 2))
+    b2b = {sb.name: time_back_to_back(sb, "fused", max(20, args.steps // 2)) for sb in stacks}
+    dom_ms = b2b[dom.name]
     achieved = dom.bytes / (dom_ms * 1e-3) / 1e9
     out = {
         "metric": "fused-stack effective HBM GB/s (algorithmic bytes / time), 1 GPU",
@@ -677,8 +528,13 @@ def main():
         "layer_by_layer": None if args.no_baseline else {
             "ms_per_step": round(ms_lbl, 4),
             "GBps_of_its_own_traffic": round(sum(sb.lbl_bytes for sb in stacks) / (ms_lbl * 1e-3) / 1e9, 1)},
-        "per_stack": {sb.name: {"ms_mean": round(per[sb.name], 4), "ms_min": round(mins[sb.name], 4),
-                                "GBps": round(sb.bytes / (per[sb.name] * 1e-3) / 1e9, 1),
+        # ms_back_to_back: launches of this stack alone, back to back between one HIP event pair (what the
+        # roofline entry uses; it agrees with the kernel trace).  ms_mean / ms_min: one event pair per launch
+        # inside the step loop, which adds the events' own 2 .. 3 us to every launch.
+        "per_stack": {sb.name: {"ms_back_to_back": round(b2b[sb.name], 4),
+                                "GBps": round(sb.bytes / (b2b[sb.name] * 1e-3) / 1e9, 1),
+                                "ms_mean": round(per[sb.name], 4), "ms_min": round(mins[sb.name], 4),
+                                "GBps_single_event_pair": round(sb.bytes / (per[sb.name] * 1e-3) / 1e9, 1),
                                 "variant": [q["variant_name"] for q in sb.info["sequences"]]}
                       for sb in stacks},
         "roofline": {"bound": "hbm", "kernel": "pool_direct_kernel<f32,4,2,2> on 32x64x224x224",
@@ -688,11 +544,17 @@ def main():
                      "avg_launch_ms_single_event_pair": round(per[dom.name], 4)},
         "context": PAPER_CONTEXT,
     }
+    # HBM bytes per launch from hardware counters are not measured by this run: they are the figure
+    # recorded in profiles/traffic.json (from two rocprofv3 --pmc runs of `bench.py --probe`, see
+    # profiles/pool_direct_vgg_hbm_traffic.md), and `traffic_source` says so
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         try:
             with open(traffic_file) as f:
-                out["roofline"]["traffic"] = json.load(f).get("vgg_a_f32_bytes_per_launch")
+                tj = json.load(f)
+            out["roofline"]["traffic"] = tj.get("vgg_a_f32_bytes_per_launch")
+            out["roofline"]["traffic_source"] = ("stored: profiles/traffic.json (" + str(tj.get("measured", "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")) +
+                                                 "), not measured by this run")
         except Exception:
             pass
     if not args.no_cpu:
@@ -700,17 +562,17 @@ def main():
     else:
         out["cpu_baseline"] = None
 
+    if not args.no_all_configs and not args.all:
+        del stacks
+        stacks = None
+        torch.cuda.empty_cache()
+        out["all_configs"] = all_configs_summary()
+    if args.batch_fit:
+        stacks = None
+        torch.cuda.empty_cache()
+        out["batch_fit"] = batch_fit()
     if args.deep:
         out["deep_stacks"] = deep_stacks()
-    if args.frontend:
-        out["frontend"] = frontend_stacks()
-    if args.networks:
-        out["networks"] = frontend_network()
-        out["networks_channels_last"] = frontend_network(dtypes=("float16",), channels_last=True)
-    if args.batch_scaling:
-        # Section 5.4: how both sides scale with the batch size, three networks
-        out["batch_scaling"] = {str(b): frontend_network(batch=b, names=("vgg16_bn", "resnet50", "densenet121"),
-                                                         dtypes=("float32",))["rows"] for b in (1, 4, 16, 64, 128)}
 
     if args.all:
         del stacks
@@ -769,8 +631,6 @@ def main():
         torch.cuda.empty_cache()
         out["backward_configs"] = backward_configs(steps=min(args.steps, 30))
         out["backward_configs_channels_last"] = backward_configs(steps=min(args.steps, 30), channels_last=True)
-        out["fine_tuning"] = frontend_training()
-        out["fine_tuning_channels_last"] = frontend_training(dtypes=("float16",), channels_last=True)
 
     if args.nhwc:
         stacks = None
