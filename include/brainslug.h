@@ -23,6 +23,9 @@
  *     stack share the dtype; BatchNorm parameters are always float32.
  *   - "host" / "device" at each pointer says where the memory lives.  The caller
  *     owns every buffer it passes; the library copies what it keeps.
+ *   - Enumerations cross the boundary as int32_t (bs_dtype in bs_stack_create, bs_variant and bs_layout in
+ *     the option block), sizes as uint64_t and the HIP stream as void *, so that the header needs no HIP
+ *     header and has one layout for every compiler.
  *   - Every function returning bs_status returns BS_OK (0) on success and leaves
  *     its outputs untouched on failure.  No function throws or aborts.
  *   - A handle may be used from one thread at a time for create/plan/destroy;
@@ -238,7 +241,9 @@ typedef struct bs_sequence_info {
 BS_API bs_status bs_stack_create(const bs_layer_desc *layers, int32_t n_layers,
                                  const int64_t in_shape[4], int32_t dtype /* bs_dtype */, bs_stack **out);
 
-/* Free the handle, its host copies and its device parameter table.  NULL is allowed. */
+/* End of a stack's life (Section 4.2: the plan made in the compile phase serves every later
+ * execution of the network; nothing of it outlives the handle): frees the handle, its host
+ * copies, its plans and its device parameter table.  NULL is allowed. */
 BS_API void bs_stack_destroy(bs_stack *stack);
 
 /* Output size of the stack (Section 4.2: the scheduler calculates the output
@@ -269,13 +274,20 @@ BS_API bs_status bs_stack_folded_bn(const bs_stack *stack, int32_t layer, float 
  */
 BS_API bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts);
 
+/* What the collapse process of Section 4.1 made of the stack: the counts of operations, steps
+ * and sequences (Listing 1), each step's operation range (Listing 2 prints exactly this
+ * partition), and per sequence the kernel family, tile, halo, on-chip bytes and grid the
+ * resource model chose.  Host only.  Errors: BS_ERR_NULL, BS_ERR_NOT_PLANNED, BS_ERR_RANGE. */
 BS_API bs_status bs_stack_plan_info(const bs_stack *stack, bs_plan_info *info);
 BS_API bs_status bs_stack_step_info(const bs_stack *stack, int32_t step, bs_step_info *info);
 BS_API bs_status bs_stack_sequence_info(const bs_stack *stack, int32_t sequence, bs_sequence_info *info);
 /* Static name of operation `op` of the plan ("BatchNorm", "ReLU", "Add", "MaxPooling",
  * "AvgPooling", "AvgNormalization"), or NULL when out of range / not planned. */
 BS_API const char *bs_stack_operation_name(const bs_stack *stack, int32_t op);
-/* Device bytes bs_stack_run needs as workspace (0 when the stack is one sequence). */
+/* Device bytes bs_stack_run needs as workspace: sequences run one after the other (Section 4.2)
+ * and hand the tensor between them through main memory, alternating between two halves of the
+ * workspace; 0 when the stack is one sequence.  The caller's framework allocates it, like the
+ * output (Section 4.2). */
 BS_API uint64_t bs_stack_workspace_bytes(const bs_stack *stack);
 
 /*

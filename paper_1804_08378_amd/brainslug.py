@@ -505,10 +505,8 @@ class Stack:
         gx = torch.empty_like(x, memory_format=mf) if need_input_grad else None
         gres = [torch.empty_like(r, memory_format=mf) if need else None for r, need in zip(residuals, need_res)]
         n = self._bwd_workspace_bytes
-        if n and (self._bwd_workspace is None or self._bwd_workspace.numel() < n or self._bwd_workspace.device != x.device):
-            self._bwd_workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
-        ws = self._bwd_workspace if n else None
         st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        ws = self.workspace(x.device, st, backward=True)
         if indices is not None:
             if len(indices) != self.n_idx:
                 raise ValueError(f"the stack has {self.n_idx} index outputs")
@@ -543,12 +541,30 @@ class Stack:
                for i in range(self.n_idx)] if indices else []
         return out, idx
 
-    def workspace(self, device="cuda"):
+    def workspace(self, device="cuda", stream=None, backward=False):
+        """The workspace for launches on `stream` (a raw stream handle; None: torch's current
+        stream): one buffer per stream, because the library's promise that runs on different
+        streams may overlap holds only when they do not share the buffer the sequences hand
+        their intermediate tensors through."""
         import torch
-        n = self._workspace_bytes
-        if n and (self._workspace is None or self._workspace.numel() < n):
-            self._workspace = torch.empty(n, dtype=torch.uint8, device=device)
-        return self._workspace if n else None
+        n = self._bwd_workspace_bytes if backward else self._workspace_bytes
+        if not n:
+            return None
+        dev = torch.device(device)
+        if stream is None:
+            stream = torch.cuda.current_stream(dev).cuda_stream
+        cache = self._bwd_workspace if backward else self._workspace
+        if cache is None:
+            cache = {}
+            if backward:
+                self._bwd_workspace = cache
+            else:
+                self._workspace = cache
+        key = (dev.index if dev.index is not None else torch.cuda.current_device(), int(stream or 0))
+        ws = cache.get(key)
+        if ws is None or ws.numel() < n:
+            ws = cache[key] = torch.empty(n, dtype=torch.uint8, device=dev)
+        return ws
 
     def run(self, x, residuals=(), out=None, indices=None, stream=None):
         """Enqueue on `stream` (default: torch's current stream); returns (out, indices).
@@ -570,8 +586,8 @@ class Stack:
         if tuple(out.shape) != self.out_shape or out.dtype != self.torch_dtype() or batch_stride(out) is None:
             raise ValueError("out must be a tensor of the stack's output shape and dtype, contiguous or a "
                              "channel slice of a contiguous tensor")
-        ws = self.workspace(x.device)
         st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        ws = self.workspace(x.device, st)
         res = [r.data_ptr() for r in residuals]
         idx = [t.data_ptr() if t is not None else 0 for t in indices] if indices else None
         wsp, wsn = (ws.data_ptr(), ws.numel()) if ws is not None else (0, 0)
@@ -593,15 +609,14 @@ class Stack:
         fast = self._fast
         if fast is None:
             lib = load()
-            n = self._workspace_bytes
-            ws = self.workspace(x.device)
             fast = self._fast = (lib.bs_stack_run_strided, C.c_void_p(self.handle),
-                                 C.c_void_p * max(1, self.n_res), ws.data_ptr() if ws is not None else None, n,
+                                 C.c_void_p * max(1, self.n_res), self._workspace_bytes,
                                  getattr(torch._C, "_cuda_getCurrentRawStream", None), x.device.index)
-        fn, h, res_type, wsp, wsn, raw_stream, dev = fast
+        fn, h, res_type, wsn, raw_stream, dev = fast
         # a fresh pointer array per call: the library reads it while the interpreter lock is released
         res = res_type(*[r.data_ptr() for r in residuals]) if residuals else None
         st = raw_stream(dev) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        wsp = self.workspace(x.device, st).data_ptr() if wsn else None  # one buffer per stream
         idx = (C.c_void_p * len(indices))(*[t.data_ptr() for t in indices]) if indices else None
         rc = fn(h, x.data_ptr(), in_batch_stride, res, out.data_ptr(), out_batch_stride, idx, wsp, wsn, st)
         if rc != 0:
@@ -617,8 +632,6 @@ class Stack:
         if not self._bwd_planned:
             self.plan_backward()
         n = self._bwd_workspace_bytes
-        if n and (self._bwd_workspace is None or self._bwd_workspace.device != x.device):
-            self._bwd_workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
         ptr = C.c_void_p * max(1, self.n_res)
         res = ptr(*[r.data_ptr() for r in residuals]) if residuals else None
         gres = ptr(*[g.data_ptr() if g is not None else None for g in grad_residuals]) if grad_residuals else None
@@ -627,7 +640,7 @@ class Stack:
         st = raw_stream(x.device.index) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
         rc = load().bs_stack_backward(self.handle, x.data_ptr(), res, idx, grad_out.data_ptr(),
                                       grad_x.data_ptr() if grad_x is not None else None, gres,
-                                      self._bwd_workspace.data_ptr() if n else None, n, st)
+                                      self.workspace(x.device, st, backward=True).data_ptr() if n else None, n, st)
         if rc != 0:
             _check(rc, "bs_stack_backward")
 
@@ -650,8 +663,8 @@ class Stack:
         for t in indices or []:
             if t is not None and not t.is_contiguous(memory_format=cl):
                 raise ValueError("index outputs must be channels_last tensors")
-        ws = self.workspace(x.device)
         st = stream if stream is not None else torch.cuda.current_stream(x.device).cuda_stream
+        ws = self.workspace(x.device, st)
         idx = [t.data_ptr() if t is not None else 0 for t in indices] if indices else None
         wsp, wsn = (ws.data_ptr(), ws.numel()) if ws is not None else (0, 0)
         bs_stack_run(self.handle, x.data_ptr(), [r.data_ptr() for r in residuals], out.data_ptr(), idx, wsp, wsn, st)

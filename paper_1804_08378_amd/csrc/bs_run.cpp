@@ -137,6 +137,27 @@ bs_status check_buffers(const bs_stack *stack, const void *in, int64_t &in_strid
         const Span ws{workspace, 1, stack->workspace_bytes, stack->workspace_bytes};
         if (spans_overlap(ws, sout) || spans_overlap(ws, sin)) return BS_ERR_ALIAS;
     }
+    // index outputs are written like `out`: they may share bytes with nothing else
+    if (indices) {
+        for (int32_t i = 0; i < stack->n_idx; ++i) {
+            if (!indices[i]) continue;
+            const uint64_t b = numel(stack->idx_shape[i]) * 4;
+            const Span si{indices[i], 1, b, b};
+            if (spans_overlap(si, sin) || spans_overlap(si, sout)) return BS_ERR_ALIAS;
+            for (int32_t j = 0; j < stack->n_res; ++j) {
+                const uint64_t rb = numel(stack->res_shape[j]) * es;
+                if (spans_overlap(si, Span{residuals[j], 1, rb, rb})) return BS_ERR_ALIAS;
+            }
+            if (stack->workspace_bytes > 0 &&
+                spans_overlap(si, Span{workspace, 1, stack->workspace_bytes, stack->workspace_bytes}))
+                return BS_ERR_ALIAS;
+            for (int32_t j = 0; j < i; ++j) {
+                if (!indices[j]) continue;
+                const uint64_t jb = numel(stack->idx_shape[j]) * 4;
+                if (spans_overlap(si, Span{indices[j], 1, jb, jb})) return BS_ERR_ALIAS;
+            }
+        }
+    }
 
     return BS_OK;
 }

@@ -1,5 +1,5 @@
 // Stack handle: validation of the layer list, host copies, BatchNorm folding and
-// the shape queries of the scheduler (Section 4.2: "calculates the output size").
+// the shape queries of the scheduler (Section 4.2).
 // Pure host code: nothing in this file touches a device.
 #include <cmath>
 #include <cstring>

@@ -56,8 +56,9 @@ def layer_desc(m: nn.Module) -> Optional[dict]:
         c = m.num_features
         ones, zeros = np.ones(c, np.float32), np.zeros(c, np.float32)
         f = lambda t, d: d if t is None else t.detach().float().cpu().numpy()
+        # "module": where the parameters come from, so that a stack can notice when they change
         return {"kind": "bn", "gamma": f(m.weight, ones), "beta": f(m.bias, zeros),
-                "mean": f(m.running_mean, zeros), "var": f(m.running_var, ones), "eps": float(m.eps)}
+                "mean": f(m.running_mean, zeros), "var": f(m.running_var, ones), "eps": float(m.eps), "module": m}
     if isinstance(m, nn.ReLU):
         return {"kind": "relu"}
     if isinstance(m, nn.LeakyReLU):
@@ -191,6 +192,42 @@ class BrainSlugStack(nn.Module):
         self.channels = next((len(l["gamma"]) for l in self.layers if l["kind"] == "bn"), None)
         self.plan_opts = dict(plan_opts)
         self._plans: Dict[tuple, bs.Stack] = {}
+        # BatchNorm parameters are folded when a plan is made.  The stack keeps the modules they came
+        # from (not as sub-modules: they stay where they are in the model) and looks at their tensors'
+        # versions and addresses before every call: after load_state_dict, .half(), an in-place update
+        # or a moving average the parameters are read again and the plans made anew (Section 4.2: the
+        # front-end hands over the parameter tensors at run time).  Layer descriptions without a
+        # source module (from_layers with plain arrays) are fixed.
+        object.__setattr__(self, "_bn_modules", [l.get("module") for l in layers if l["kind"] == "bn"])
+        self._bn_seen = self._bn_state()
+
+    def _bn_state(self) -> tuple:
+        st = []
+        for m in self._bn_modules:
+            if m is not None:
+                for t in (m.weight, m.bias, m.running_mean, m.running_var):
+                    st.append(None if t is None else (t.data_ptr(), t._version))
+        return tuple(st)
+
+    def sync_parameters(self) -> bool:
+        """Re-read the BatchNorm parameters from their modules if any of their tensors changed
+        since they were last read; the plans are then made anew at the next call.  Called by
+        `forward`.  Returns whether anything changed."""
+        state = self._bn_state()
+        if state == self._bn_seen:
+            return False
+        for l in self.layers:
+            if l["kind"] == "bn" and l.get("module") is not None:
+                fresh = layer_desc(l["module"])
+                if fresh is None or len(fresh["gamma"]) != len(l["gamma"]):
+                    raise RuntimeError("a BatchNorm module of a BrainSlugStack no longer is an inference-mode "
+                                       "BatchNorm of the same width")
+                l.update(fresh)
+        for st in self._plans.values():
+            st.close()
+        self._plans.clear()
+        self._bn_seen = state
+        return True
 
     def extra_repr(self) -> str:
         return "replaces " + " -> ".join(self.replaced)
@@ -253,6 +290,8 @@ class BrainSlugStack(nn.Module):
                 raise RuntimeError("residual operands must have the input's shape (no broadcasting)")
             flat = self.forward(x.contiguous().view(1, 1, 1, -1), *[r.contiguous().view(1, 1, 1, -1) for r in residuals])
             return flat.view(x.shape)
+        if self._bn_seen:
+            self.sync_parameters()
         if self.channels is not None and x.shape[1] != self.channels:
             raise RuntimeError(f"expected {self.channels} channels, got {x.shape[1]}")
         if torch.is_grad_enabled() and (x.requires_grad or any(r.requires_grad for r in residuals)):

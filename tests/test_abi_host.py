@@ -200,6 +200,48 @@ def test_backward_stages_and_workspace():
     assert _backward_plan([wl.add()] * 5, shape)[0] == 2
 
 
+def test_index_outputs_may_share_bytes_with_nothing():
+    """Index outputs are written by the kernels like the output itself: one that overlaps the
+    input, the output, a residual operand, the workspace or another index output is refused
+    (host only, fake addresses; the expectation comes from explicit byte ranges)."""
+    n, c, h, w = 2, 2, 8, 8
+    layers = [wl.maxpool(2, 2, 0, True), wl.add(), wl.maxpool(2, 2, 0, True)]
+    hd = bs.bs_stack_create(layers, (n, c, h, w), "f32")
+    try:
+        bs.bs_stack_plan(hd, host_only=1, max_steps_per_sequence=1)
+        wsn = bs.bs_stack_workspace_bytes(hd)
+        assert wsn > 0
+        sizes = {"in": n * c * h * w * 4, "res": n * c * 16 * 4, "out": n * c * 4 * 4, "ws": wsn,
+                 "i0": n * c * 16 * 4, "i1": n * c * 4 * 4}
+        base = {"in": 1 << 20, "res": 2 << 20, "out": 3 << 20, "ws": 4 << 20, "i0": 5 << 20, "i1": 6 << 20}
+
+        def status(**moved):
+            p = dict(base, **moved)
+            return bs.bs_stack_check_buffers(hd, p["in"], 0, [p["res"]], p["out"], 0, [p["i0"], p["i1"]], p["ws"], wsn)
+
+        def overlap(p, a, b):
+            return p[a] < p[b] + sizes[b] and p[b] < p[a] + sizes[a]
+
+        assert status() == 0
+        rng = np.random.default_rng(11)
+        hits = 0
+        for which in ("i0", "i1"):
+            for other in ("in", "res", "out", "ws", "i1" if which == "i0" else "i0"):
+                for _ in range(20):
+                    off = 16 * int(rng.integers(-(sizes[which] // 16) - 2, sizes[other] // 16 + 3))
+                    moved = {which: base[other] + off}
+                    p = dict(base, **moved)
+                    truth = any(overlap(p, which, o) for o in p if o != which)
+                    assert status(**moved) == (12 if truth else 0), (which, other, off)
+                    hits += truth
+        assert hits > 40
+        # a skipped index output (NULL) takes part in nothing
+        assert bs.bs_stack_check_buffers(hd, base["in"], 0, [base["res"]], base["out"], 0, [0, base["in"]], base["ws"], wsn) == 12
+        assert bs.bs_stack_check_buffers(hd, base["in"], 0, [base["res"]], base["out"], 0, [0, base["i1"]], base["ws"], wsn) == 0
+    finally:
+        bs.bs_stack_destroy(hd)
+
+
 def test_size_limit_is_two_to_the_31_elements():
     """All index arithmetic is 32-bit: a tensor (input, output or intermediate) of 2^31 elements
     or more is refused at create, one just below is accepted and plans (host only)."""

@@ -839,3 +839,54 @@ def test_stack_under_autograd_keeps_only_its_operands():
         assert not stack(x).requires_grad
     assert not stack(x.detach()).requires_grad
     stack.close()
+
+
+def test_stacks_notice_changed_batchnorm_parameters():
+    """A stack folds the BatchNorm parameters when it plans; it keeps the modules they come from and
+    re-reads them when one of their tensors was modified or replaced (Section 4.2: the parameter
+    tensors are gathered at run time)."""
+    bn = nn.BatchNorm2d(3).eval()
+    stack = fe.BrainSlugStack([bn, nn.ReLU()])
+    assert not stack.sync_parameters()
+    assert np.array_equal(stack.layers[0]["gamma"], np.ones(3, np.float32))
+    with torch.no_grad():
+        bn.weight.mul_(2.0)  # in place: same storage, new version
+    assert stack.sync_parameters() and not stack.sync_parameters()
+    assert np.array_equal(stack.layers[0]["gamma"], 2 * np.ones(3, np.float32))
+    state = {k: v.clone() for k, v in bn.state_dict().items()}
+    state["running_mean"] = torch.tensor([1.0, 2.0, 3.0])
+    bn.load_state_dict(state)
+    assert stack.sync_parameters()
+    assert np.array_equal(stack.layers[0]["mean"], np.array([1, 2, 3], np.float32))
+    bn.double()  # replaces the buffers and the parameters' storage
+    assert stack.sync_parameters()
+    assert stack.layers[0]["gamma"].dtype == np.float32
+    # plain arrays have no source: such a stack is fixed
+    fixed = fe.BrainSlugStack.from_layers([{k: v for k, v in stack.layers[0].items() if k != "module"}, {"kind": "relu"}],
+                                          ["BatchNorm2d", "ReLU"])
+    assert fixed._bn_seen == () and not fixed.sync_parameters()
+
+
+@pytest.mark.gpu
+def test_changed_batchnorm_parameters_reach_the_kernels():
+    ref = vgg_like(width=8).cuda()
+    x = torch.randn(2, 3, 24, 24, device="cuda")
+    with torch.no_grad():
+        ref(x)
+    opt = fe.optimize(ref, lone_activations=True)  # rewritten in place: `ref`'s BatchNorm modules are the stacks' sources
+    bns = [m for s in opt.optimized_stacks for m in s._bn_modules]
+    assert bns
+    with torch.no_grad():
+        before = opt(x).clone()
+        for m in bns:
+            m.weight.mul_(-1.5)
+            m.running_mean.add_(0.25)
+        after = opt(x)
+    assert (after - before).abs().max().item() > 1e-3
+    for i, stack in enumerate(opt.optimized_stacks):
+        for l in stack.layers:
+            if l["kind"] == "bn":
+                assert np.array_equal(l["gamma"], l["module"].weight.detach().cpu().numpy())
+                assert np.array_equal(l["mean"], l["module"].running_mean.cpu().numpy())
+    for s in opt.optimized_stacks:
+        s.close()

@@ -1002,3 +1002,35 @@ def test_signed_zero_and_subnormals_follow_the_oracle():
         if want:
             assert np.array_equal(out.view(np.uint32), ref.view(np.uint32))
             assert np.array_equal(idx[0], ridx[0])
+
+
+def test_one_planned_handle_runs_on_two_streams_at_once():
+    """bs_stack_run does not modify the handle: two streams may run one planned stack at the same
+    time on different buffers -- each with a workspace of its own, since the stack here is
+    several sequences.  Many launches are queued on both streams before anything is waited for,
+    so the kernels of the two streams do overlap; every result must be the oracle's."""
+    c = 8
+    layers = sum(([wl.maxpool(3, 1, 1, i == 1), wl.bn_params(c, 500 + i), wl.relu()] for i in range(4)), [])
+    shape = (16, c, 56, 56)
+    xs = [wl.activation(shape, 60 + i) for i in range(2)]
+    refs = [bf.run_stack(layers, x, [], "f32") for x in xs]
+    st = bs.Stack(layers, shape, "f32").plan(max_steps_per_sequence=1)
+    assert st.info()["n_sequences"] == 4 and st.info()["workspace_bytes"] > 0
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    xd = [_dev(x, "f32") for x in xs]
+    rounds = 6
+    outs = [[st.alloc_outputs("cuda") for _ in range(rounds)] for _ in streams]
+    torch.cuda.synchronize()
+    for r in range(rounds):
+        for i, s in enumerate(streams):
+            o, idx = outs[i][r]
+            st.run(xd[i], [], out=o, indices=idx, stream=s.cuda_stream)
+    torch.cuda.synchronize()
+    assert len(st._workspace) == 2, "one workspace per stream"
+    for i in range(2):
+        ref, ref_idx, _ = refs[i]
+        for r in range(rounds):
+            o, idx = outs[i][r]
+            assert np.array_equal(o.cpu().numpy().view(np.uint32), ref.view(np.uint32)), (i, r)
+            assert np.array_equal(idx[0].cpu().numpy(), ref_idx[0]), (i, r)
+    st.close()
