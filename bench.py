@@ -210,6 +210,71 @@ def batch_fit(configs=(("vgg_c", "f32"), ("densenet_trans", "f32"), ("resnet_ste
     return rows
 
 
+def issue_rates(iterations=20000, clock_ghz=2.4):
+    """Cycles per instruction group per SIMD (and per wave) for the kinds of bs_probe_issue_rate,
+    with 1, 2, 4 and 8 waves per SIMD: the issue limits that bound the kernels which are not
+    bound by HBM.  Cycles are at the nominal 2.4 GHz engine clock."""
+    import torch
+    from paper_1804_08378_amd import brainslug as bs
+
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(cus * 8 * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for name, kind in bs.PROBE_KINDS.items():
+        row = {"kind": name}
+        for wps in (1, 2, 4, 8):
+            bs.bs_probe_issue_rate(kind, wps, 200, sink.data_ptr(), sink.numel(), stream)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            bs.bs_probe_issue_rate(kind, wps, iterations, sink.data_ptr(), sink.numel(), stream)
+            b.record()
+            torch.cuda.synchronize()
+            ns = a.elapsed_time(b) * 1e6
+            row[f"cycles_per_simd_{wps}w"] = round(ns * clock_ghz / (8.0 * iterations * wps), 2)
+            row[f"cycles_per_wave_{wps}w"] = round(ns * clock_ghz / (8.0 * iterations), 2)
+        rows.append(row)
+        log(f"issue_rates {name:<14}" + "".join(f"  {w} waves/SIMD: {row[f'cycles_per_simd_{w}w']:6.2f} per SIMD, "
+                                                f"{row[f'cycles_per_wave_{w}w']:6.1f} per wave;" for w in (1, 2, 4, 8)))
+    return rows
+
+
+def launch_only(spec, launches):
+    """`launches` launches of one configuration and nothing else (no timing): the leg for
+    rocprofv3 counter and kernel-trace runs.  spec = NAME:DTYPE[:key=value,...]; NAME is a
+    benchmark configuration or deepN (N blocks of MaxPool 3/1/1 -> BatchNorm -> ReLU on
+    64 x 64 x 56 x 56); the keys are plan options (layout=1, lane_exchange=-1, force_variant=3,
+    max_steps_per_sequence=5 ...) and indices=1."""
+    import torch
+    from paper_1804_08378_amd import brainslug as bs
+    from paper_1804_08378_amd import workloads as wl
+
+    parts = spec.split(":")
+    name, dt = parts[0], parts[1]
+    opts = dict(kv.split("=") for kv in parts[2].split(",")) if len(parts) > 2 and parts[2] else {}
+    opts = {k: int(v) for k, v in opts.items()}
+    indices = bool(opts.pop("indices", 0))
+    if name.startswith("deep"):
+        c, n = 64, int(name[4:])
+        layers = sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 100 + i), wl.relu()] for i in range(n)), [])
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dt]
+        st = bs.Stack(layers, (64, c, 56, 56), dt).plan(**opts)
+        xs = [torch.randn(64, c, 56, 56, device="cuda").to(tdt) for _ in range(4)]
+        outs = [st.alloc_outputs("cuda", False)[0] for _ in range(4)]
+        for i in range(launches):
+            st.run(xs[i % 4], out=outs[i % 4], indices=[])
+        info = st.info()
+    else:
+        sb = StackBench(name, dt, indices=indices, **opts)
+        for _ in range(launches):
+            sb.launch("fused")
+        info = sb.info
+    torch.cuda.synchronize()
+    log("launched", spec, "x", launches, "sequences:",
+        [(q["variant_name"], q["grid"], q["threads_per_group"], q["tile_rows"]) for q in info["sequences"]])
+
+
 def cpu_baseline(names, dtype, batch, passes):
     """Time the breadth-first CPU oracle, as it stands, on the same stacks: `passes` passes over
     the workload at `batch` images with all host threads, plus one single-thread pass."""
@@ -459,6 +524,10 @@ def main():
     ap.add_argument("--batch-fit", action="store_true",
                     help="also time the pooling configurations at 1/4 .. 4 times their batch size and fit "
                          "time = fixed cost + bytes / rate")
+    ap.add_argument("--issue-rates", action="store_true",
+                    help="also measure the device's instruction issue rates (bs_probe_issue_rate)")
+    ap.add_argument("--launch", nargs=2, metavar=("SPEC", "N"),
+                    help="only launch one configuration N times (for rocprofv3): SPEC = NAME:DTYPE[:key=value,...]")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
                     help="counter probe for rocprofv3 --pmc: N launches of a plain copy of known size, "
                          "then N launches of each VGG stack; no timing, no JSON")
@@ -477,6 +546,10 @@ def main():
         sys.exit(2)
     bs.load()
     log(bs.bs_version(), "|", torch.cuda.get_device_name(0))
+
+    if args.launch:
+        launch_only(args.launch[0], int(args.launch[1]))
+        return
 
     if args.probe:
         # a copy of exactly 256 MiB in and 256 MiB out calibrates the byte counters
@@ -567,6 +640,8 @@ def main():
         stacks = None
         torch.cuda.empty_cache()
         out["all_configs"] = all_configs_summary()
+    if args.issue_rates:
+        out["issue_rates"] = issue_rates()
     if args.batch_fit:
         stacks = None
         torch.cuda.empty_cache()

@@ -439,6 +439,30 @@ BS_API bs_status bs_stack_jit_check(const bs_stack *stack, const char *arch, int
  * pointer stays valid until the calling thread's next call of this function. */
 BS_API const char *bs_jit_log(void);
 
+/*
+ * Measurement aid (the resource model of Section 4.1 and the utilisation trade-offs of Section 4.4
+ * need the device's issue rates, which no query reports): enqueue a kernel in which every wave
+ * issues 8 * `iterations` instruction groups of one kind and nothing else, on
+ * `waves_per_simd` (1..8) waves per SIMD of every compute unit.  The caller times the launch;
+ * cycles per group per SIMD = time * clock / (8 * iterations * waves_per_simd).
+ *   kind         bs_probe_kind
+ *   sink         device, >= compute units * waves_per_simd * 256 floats (one store per lane)
+ * Errors: BS_ERR_NULL, BS_ERR_PARAM, BS_ERR_RANGE (kind), BS_ERR_WORKSPACE (sink too small), BS_ERR_HIP.
+ */
+typedef enum bs_probe_kind {
+    BS_PROBE_ADD = 0,           /* v_add_f32 (two-operand encoding)                          */
+    BS_PROBE_FMA = 1,           /* v_fma_f32 (three-operand encoding)                        */
+    BS_PROBE_MAX3 = 2,          /* v_max3_f32                                                */
+    BS_PROBE_SELECT_VCC = 3,    /* v_cndmask_b32 reading its lane mask from VCC              */
+    BS_PROBE_SELECT_SGPR = 4,   /* v_cndmask_b32 reading its lane mask from a scalar pair    */
+    BS_PROBE_LANE_SHIFT = 5,    /* v_mov_b32 with a one-lane wave shift (DPP)                */
+    BS_PROBE_ADD_SCALAR = 6,    /* group = v_add_f32 + one scalar ALU instruction            */
+    BS_PROBE_ADD_BRANCH = 7,    /* group = v_add_f32 + one not-taken scalar branch           */
+    BS_PROBE_DEPENDENT_ADD = 8  /* v_add_f32 on one register: every add waits for the last   */
+} bs_probe_kind;
+BS_API bs_status bs_probe_issue_rate(int32_t kind, int32_t waves_per_simd, int32_t iterations, float *sink,
+                                     uint64_t sink_floats, void *stream);
+
 /* Static, never NULL. */
 BS_API const char *bs_status_string(bs_status status);
 BS_API const char *bs_version(void);

@@ -110,6 +110,7 @@ _SIGNATURES = {
     "bs_stack_backward_num_stages": (C.c_int32, [C.c_void_p]),
     "bs_stack_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p,
                                     C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_probe_issue_rate": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_uint64, C.c_void_p]),
     "bs_stack_jit_check": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]),
     "bs_jit_log": (C.c_char_p, []),
     "bs_status_string": (C.c_char_p, [C.c_int]),
@@ -350,6 +351,15 @@ def bs_stack_run_static(handle, in_ptr, residual_ptrs, out_ptr, index_ptrs, stre
 
 def bs_static_workspace_capacity() -> int:
     return int(load().bs_static_workspace_capacity())
+
+
+PROBE_KINDS = {"add": 0, "fma": 1, "max3": 2, "select_vcc": 3, "select_sgpr": 4, "lane_shift": 5, "add_scalar": 6,
+               "add_branch": 7, "dependent_add": 8}
+
+
+def bs_probe_issue_rate(kind: int, waves_per_simd: int, iterations: int, sink_ptr: int, sink_floats: int, stream) -> None:
+    _check(load().bs_probe_issue_rate(int(kind), int(waves_per_simd), int(iterations), C.c_void_p(sink_ptr or None),
+                                      int(sink_floats), C.c_void_p(stream or None)), "bs_probe_issue_rate")
 
 
 def bs_stack_plan_backward(handle) -> None:
