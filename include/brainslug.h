@@ -136,7 +136,8 @@ typedef enum bs_variant {
     BS_VARIANT_POOL_ROWS = 4,   /* one or two pooling steps with overlapping / padded windows: rows slide in registers, no LDS */
     BS_VARIANT_PLANE_POOL = 5,  /* one step whose window is the whole (small) plane: one lane per plane       */
     BS_VARIANT_NHWC_STREAM = 6, /* channels-last plans only: element-wise, one channel vector per lane   */
-    BS_VARIANT_NHWC_POOL = 7    /* channels-last plans only: one pooling step, a lane = one output pixel x one channel vector */
+    BS_VARIANT_NHWC_POOL = 7,   /* channels-last plans only: one pooling step, a lane = one output pixel x one channel vector */
+    BS_VARIANT_NHWC_TILE = 8    /* channels-last plans only: two pooling steps, tiles of both planes with halos staged in LDS */
 } bs_variant;
 
 /* Memory order of every tensor of a planned stack (shapes are always given as N, C, H, W). */

@@ -53,6 +53,7 @@ struct Sequence {
     PoolRows2K rows2{};
     LdsSeqK lds{};
     NhwcK nhwc{};
+    NhwcTile2K nhwc2{};
     // run-time build (hipFunction_t) without / with index outputs; null = pre-compiled kernel
     int32_t jit = 0;
     void *jit_fn[2] = {nullptr, nullptr};
@@ -156,6 +157,11 @@ void nhwc_block(const PoolK &p, int32_t vec, int32_t dtype, int32_t &ohb, int32_
 int32_t nhwc_plane_group(int64_t hw, int32_t vec, const PoolK &p, int32_t H, int32_t W, int32_t Ho, int32_t Wo);
 bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, uint64_t lds_bytes,
                       void *stream);
+// bs_nhwc_tile.hip: channels-last, two pooling steps per sequence
+bool nhwc_tile2_supported(const PoolK &pool1, const PoolK &pool2);
+uint64_t nhwc_tile2_lds(const PoolK &p1, const PoolK &p2, int32_t th, int32_t tw, int32_t cvb, int32_t (&r0)[2], int32_t (&r1)[2]);
+bs_status launch_nhwc_tile2(const NhwcTile2K &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, uint64_t lds_bytes,
+                            void *stream);
 // bs_rows.hip: *_supported = the signature is in the pre-compiled table; *_buildable = the
 // kernel template can be instantiated for it at run time; *_expr = that instance's name
 bool rows_supported(const PoolK &pool, const EwOp *pre, int32_t n_pre, const EwOp *post, int32_t n_post);

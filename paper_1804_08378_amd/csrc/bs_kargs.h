@@ -215,6 +215,26 @@ struct NhwcK {
                       // div_wo then divides by the work-groups per image
 };
 
+// Channels-last sequence of two pooling steps in one kernel (bs_nhwc_tile.hip): a work-group owns
+// TH x TW output pixels of one image and `cvb` consecutive channel vectors, and keeps the rectangles
+// of the input plane (r0h x r0w cells) and of the plane between the pools (r1h x r1w) under them in LDS.
+struct NhwcTile2K {
+    const void *in;
+    void *out;
+    const float *params;
+    const void *res[K_MAX_RES];
+    int32_t *idx;                // picks of the second pool (a max pool), or null
+    int32_t n_pre, n_mid, n_post;
+    EwOp pre[K_MAX_EW], mid[K_MAX_EW], post[K_MAX_EW];
+    PoolK pool1, pool2;
+    int32_t C, H, W, H1, W1, Ho, Wo;
+    int32_t TH, TW, r0h, r0w, r1h, r1w;
+    int32_t cvb, pl;             // channel vectors per work-group; pixel lanes = threads / cvb
+    int32_t cvgs, tiles_h, tiles_w;  // work-groups per tile (C / vec / cvb), tiles per image
+    FastDiv div_cvb, div_r0w, div_r1w, div_tw, div_cvgs, div_tiles_w, div_tiles_h;
+    uint32_t in_xp, out_xp;      // as in NhwcK
+};
+
 // Backward pass of one stage: element-wise operations followed by at most one pooling
 // operation (pool.kind == 0: none).  Dense tensors only, row-major (NCHW) or channels-last.
 constexpr int K_BWD_EW = 16;

@@ -18,80 +18,12 @@
 // output rounded to the storage type), so the results are the same numbers in another
 // memory order.  Index outputs hold ih * W + iw like the NCHW ones and are laid out like
 // the output tensor.
-#include "bs_device.h"
+#include "bs_nhwc_device.h"
 #include <algorithm>
 
 #include "bs_internal.h"
 
 namespace bs {
-
-// VEC consecutive float32 parameters starting at element `off` (a multiple of VEC; BatchNorm
-// tables start at multiples of 8 floats): 128-bit loads, served by the caches.
-template <int VEC>
-BS_DEV void load_params(const float *__restrict__ params, uint32_t off, float (&v)[VEC])
-{
-    if constexpr (VEC % 4 == 0) {
-#pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-            const float4 t = *reinterpret_cast<const float4 *>(params + off + 4 * q);
-            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) v[i] = params[off + i];
-    }
-}
-
-// Apply an element-wise list to U register vectors that all hold channels c0 .. c0 + VEC - 1.
-//   off[u]  element offset of vector u in this level's tensors (residual loads)
-template <int DT, int VEC, int U>
-BS_DEV void apply_ew_nhwc(float (&x)[U][VEC], uint32_t c0, const uint32_t (&off)[U], const EwOp *ew,
-                          int32_t n_ew, const float *__restrict__ params, int32_t C, const void *const *res)
-{
-#pragma clang loop unroll(disable)
-    for (int32_t j = 0; j < n_ew; ++j) {
-        const int32_t kind = ew[j].kind, arg = ew[j].arg;
-        if (kind == OP_BN) {
-            float sc[VEC], sh[VEC];
-            load_params<VEC>(params, (uint32_t)arg + c0, sc);
-            load_params<VEC>(params, (uint32_t)(arg + C) + c0, sh);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(__builtin_fmaf(x[u][i], sc[i], sh[i]));
-        } else if (kind == OP_RELU) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = __builtin_fmaxf(x[u][i], 0.0f);  // NaN, -0 -> +0
-        } else if (kind == OP_LEAKY) {
-            const float slope = params[arg];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(x[u][i] > 0.0f ? x[u][i] : x[u][i] * slope);
-        } else if (kind == OP_CLAMP) {
-            const float lo = params[arg], hi = params[arg + 1];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i)
-                    x[u][i] = round_store<DT>(__builtin_fminf(__builtin_fmaxf(x[u][i], lo), hi));
-        } else {  // OP_ADD
-            const void *rp = res[arg];
-            Raw<DT, VEC> rr[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) rr[u] = load_raw<DT, VEC, true>(rp, off[u]);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float r[VEC];
-                unpack<DT, VEC>(rr[u], r);
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(x[u][i] + r[i]);
-            }
-        }
-    }
-}
 
 // Element-wise only.  A work-group takes nthr * U consecutive vectors; lane t handles vectors
 // t, t + nthr, ...
@@ -160,19 +92,6 @@ BS_DEV void take_cell(bool is_max, const float (&v)[VEC], int32_t cell_index, fl
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = acc[e] + v[e];
     }
-}
-
-// float32 reciprocal of the average's divisor for the window at (h0, w0), in-range part
-// [hlo, hhi) x [wlo, whi)
-BS_DEV float avg_inv(const PoolK &p, int32_t kh, int32_t kw, int32_t H, int32_t W, int32_t h0, int32_t w0,
-                     int32_t hlo, int32_t hhi, int32_t wlo, int32_t whi)
-{
-    if (!p.count_include_pad) return 1.0f / (float)max((hhi - hlo) * (whi - wlo), 1);
-    if (p.count_include_pad == 2) {  // ceil mode: cells inside the padded plane
-        const int32_t nr = min(h0 + kh, H + p.ph) - h0, nc = min(w0 + kw, W + p.pw) - w0;
-        return 1.0f / (float)max(nr * nc, 1);
-    }
-    return p.inv_kk;
 }
 
 // One pooling operation with a compile-time window KH x KW and strides SH x SW.  A lane

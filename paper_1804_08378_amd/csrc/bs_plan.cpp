@@ -423,6 +423,29 @@ static void plan_stream(const bs_stack *s, Sequence &q)
     q.planes_per_group = 0;
 }
 
+// Does an element-wise list give the same value applied to a maximum as the maximum of the list
+// applied to every cell?  True when no operation decreases as its input increases (BatchNorm
+// with scales >= 0, ReLU, leaky ReLU with a slope >= 0, clamp; rounding to the storage type is
+// of that kind too) -- then max_i f(x_i) = f(max_i x_i), the same float32 value, up to the sign
+// of a zero -- and the list holds a ReLU, which makes every zero +0.
+static bool commutes_with_max(const bs_stack *s, const EwOp *ew, int32_t n, int32_t C)
+{
+    bool monotone = true, relu = false;
+    for (int32_t j = 0; j < n && monotone; ++j) {
+        const EwOp &e = ew[j];
+        if (e.kind == OP_BN) {
+            for (int32_t c = 0; c < C; ++c) monotone = monotone && s->host_params[(size_t)e.arg + c] >= 0.0f;
+        } else if (e.kind == OP_LEAKY) {
+            monotone = s->host_params[(size_t)e.arg] >= 0.0f;
+        } else if (e.kind == OP_RELU) {
+            relu = true;
+        } else if (e.kind != OP_CLAMP) {
+            monotone = false;  // a residual Add differs from cell to cell
+        }
+    }
+    return monotone && relu;
+}
+
 // Channels-last sequence: element-wise only, or one pooling step.
 static bs_status plan_nhwc(const bs_stack *s, Sequence &q)
 {
@@ -458,29 +481,15 @@ static bs_status plan_nhwc(const bs_stack *s, Sequence &q)
     // made every zero +0.  So when no argmax is wanted and the list before a max pool is of
     // that kind and holds a ReLU, the pool runs on the raw input and the list on its output:
     // once per output instead of once per window cell.
-    if (seen && k.pool.kind == OP_MAXPOOL && k.pool.idx_slot < 0 && k.n_pre > 0 && k.n_pre + k.n_post <= K_MAX_EW) {
-        bool monotone = true, relu = false;
-        for (int32_t j = 0; j < k.n_pre && monotone; ++j) {
-            const EwOp &e = k.pre[j];
-            if (e.kind == OP_BN) {
-                for (int32_t c = 0; c < C; ++c) monotone = monotone && s->host_params[(size_t)e.arg + c] >= 0.0f;
-            } else if (e.kind == OP_LEAKY) {
-                monotone = s->host_params[(size_t)e.arg] >= 0.0f;
-            } else if (e.kind == OP_RELU) {
-                relu = true;
-            } else if (e.kind != OP_CLAMP) {
-                monotone = false;  // a residual Add differs from cell to cell
-            }
-        }
-        if (monotone && relu) {
-            EwOp moved[K_MAX_EW];
-            int32_t m = 0;
-            for (int32_t j = 0; j < k.n_pre; ++j) moved[m++] = k.pre[j];
-            for (int32_t j = 0; j < k.n_post; ++j) moved[m++] = k.post[j];
-            for (int32_t j = 0; j < m; ++j) k.post[j] = moved[j];
-            k.n_post = m;
-            k.n_pre = 0;
-        }
+    if (seen && k.pool.kind == OP_MAXPOOL && k.pool.idx_slot < 0 && k.n_pre > 0 && k.n_pre + k.n_post <= K_MAX_EW &&
+        commutes_with_max(s, k.pre, k.n_pre, C)) {
+        EwOp moved[K_MAX_EW];
+        int32_t m = 0;
+        for (int32_t j = 0; j < k.n_pre; ++j) moved[m++] = k.pre[j];
+        for (int32_t j = 0; j < k.n_post; ++j) moved[m++] = k.post[j];
+        for (int32_t j = 0; j < m; ++j) k.post[j] = moved[j];
+        k.n_post = m;
+        k.n_pre = 0;
     }
     if (!seen) {
         k.H = k.Ho = (int32_t)q.in_shape[2];
@@ -528,6 +537,112 @@ static bs_status plan_nhwc(const bs_stack *s, Sequence &q)
                                       ((double)k.H * k.W);
     q.planes_per_group = 0;
     q.n_levels = seen ? 1 : 0;
+    return BS_OK;
+}
+
+// Channels-last sequence of two pooling steps: one kernel, tiles of both planes in LDS.
+// BS_ERR_UNSUPPORTED when the pair is not one the kernel exists for (the steps then run one by one).
+static bs_status plan_nhwc_tile2(const bs_stack *s, Sequence &q, const bs_plan_options &o)
+{
+    NhwcTile2K &k = q.nhwc2;
+    k = NhwcTile2K{};
+    const int32_t C = (int32_t)q.in_shape[1], vec = vec_of(s);
+    if (C % vec != 0 || count_pools(s, q.first_op, q.n_ops) != 2) return BS_ERR_UNSUPPORTED;
+    q.vec = vec;
+    int32_t pools = 0;
+    for (int32_t i = q.first_op; i < q.first_op + q.n_ops; ++i) {
+        const Op &op = s->ops[i];
+        if (!op_is_elementwise(op.kind)) {
+            if (pools == 0) {
+                if (op.idx_slot >= 0) return BS_ERR_UNSUPPORTED;  // picks inside the plane between the pools: tiles overlap there
+                k.pool1 = make_pool(op, nullptr, q);
+                k.H = op.in_h; k.W = op.in_w; k.H1 = op.out_h; k.W1 = op.out_w;
+            } else {
+                k.pool2 = make_pool(op, nullptr, q);
+                if (op.in_h != k.H1 || op.in_w != k.W1) return BS_ERR_UNSUPPORTED;
+                k.Ho = op.out_h; k.Wo = op.out_w;
+            }
+            ++pools;
+        } else if (op.kind != OP_AVGNORM) {
+            EwOp *list = pools == 0 ? k.pre : pools == 1 ? k.mid : k.post;
+            int32_t &n = pools == 0 ? k.n_pre : pools == 1 ? k.n_mid : k.n_post;
+            if (n >= K_MAX_EW) return BS_ERR_UNSUPPORTED;
+            fill_ew(s, op, q, list[n++]);
+        }
+    }
+    if (!nhwc_tile2_supported(k.pool1, k.pool2)) return BS_ERR_UNSUPPORTED;
+    k.C = C;
+    // maximum first (see plan_nhwc): a list in front of a max pool that commutes with the maximum
+    // runs once per pooled value, behind the pool
+    auto move_behind = [&](EwOp *from, int32_t &n_from, EwOp *to, int32_t &n_to) {
+        EwOp moved[K_MAX_EW];
+        int32_t m = 0;
+        for (int32_t j = 0; j < n_from; ++j) moved[m++] = from[j];
+        for (int32_t j = 0; j < n_to; ++j) moved[m++] = to[j];
+        for (int32_t j = 0; j < m; ++j) to[j] = moved[j];
+        n_to = m;
+        n_from = 0;
+    };
+    if (k.pool1.kind == OP_MAXPOOL && k.n_pre > 0 && k.n_pre + k.n_mid <= K_MAX_EW && commutes_with_max(s, k.pre, k.n_pre, C))
+        move_behind(k.pre, k.n_pre, k.mid, k.n_mid);
+    if (k.pool2.kind == OP_MAXPOOL && k.pool2.idx_slot < 0 && k.n_mid > 0 && k.n_mid + k.n_post <= K_MAX_EW &&
+        commutes_with_max(s, k.mid, k.n_mid, C))
+        move_behind(k.mid, k.n_mid, k.post, k.n_post);
+
+    // Tile and channel group.  Candidates: channel groups that divide the pixel's vectors (at
+    // most 16 per work-group), every tile up to 16 x 16 outputs whose two rectangles fit the LDS
+    // budget.  Cost of a candidate = cells a work-group touches per image at each level (input
+    // cells weigh most: a global load and the leading element-wise list), scaled up when the
+    // group's run of channels is shorter than a 128-byte line or when fewer than three
+    // work-groups fit a compute unit's LDS.
+    const int32_t cvn = C / vec;
+    const uint64_t lds_cap = std::min<uint64_t>(64 * 1024, std::max<uint64_t>(o.max_lds_bytes ? o.max_lds_bytes : 64 * 1024, 1));
+    double best = 0.0;
+    int32_t bth = 0, btw = 0, bcvb = 0;
+    for (int32_t cvb = std::min(cvn, 16); cvb >= 1; --cvb) {
+        if (cvn % cvb != 0) continue;
+        if (o.planes_per_group > 0 && cvb * vec != o.planes_per_group) continue;
+        for (int32_t th = 1; th <= std::min(16, k.Ho); ++th)
+            for (int32_t tw = 1; tw <= std::min(16, k.Wo); ++tw) {
+                if (o.tile_rows > 0 && th != std::min(o.tile_rows, k.Ho)) continue;
+                if (o.tile_cols > 0 && tw != std::min(o.tile_cols, k.Wo)) continue;
+                int32_t r0[2], r1[2];
+                const uint64_t lds = nhwc_tile2_lds(k.pool1, k.pool2, th, tw, cvb, r0, r1);
+                if (lds > lds_cap) continue;
+                const int64_t tiles = (int64_t)((k.Ho + th - 1) / th) * ((k.Wo + tw - 1) / tw);
+                const int32_t pl = 256 / cvb;
+                auto passes = [&](int64_t cells) { return (double)((cells + pl - 1) / pl) * pl; };  // lanes idle in the last pass
+                double cost = (double)tiles * (3.0 * passes((int64_t)r0[0] * r0[1]) + 2.0 * passes((int64_t)r1[0] * r1[1]) + 2.0 * passes((int64_t)th * tw));
+                if ((uint64_t)cvb * 16 < 128) cost *= 1.0 + 0.1 * (128.0 / (cvb * 16.0) - 1.0);
+                const int32_t resident = (int32_t)std::min<uint64_t>(8, (160 * 1024) / std::max<uint64_t>(lds, 1));
+                if (resident < 3) cost *= 1.0 + 0.15 * (3 - resident);
+                if (bth == 0 || cost < best) { best = cost; bth = th; btw = tw; bcvb = cvb; }
+            }
+    }
+    if (bth == 0) return BS_ERR_UNSUPPORTED;
+    int32_t r0[2], r1[2];
+    q.lds_bytes = nhwc_tile2_lds(k.pool1, k.pool2, bth, btw, bcvb, r0, r1);
+    k.TH = bth; k.TW = btw; k.cvb = bcvb; k.pl = 256 / bcvb;
+    k.r0h = r0[0]; k.r0w = r0[1]; k.r1h = r1[0]; k.r1w = r1[1];
+    k.cvgs = cvn / bcvb;
+    k.tiles_h = (k.Ho + bth - 1) / bth;
+    k.tiles_w = (k.Wo + btw - 1) / btw;
+    k.div_cvb = make_fastdiv((uint32_t)k.cvb);
+    k.div_r0w = make_fastdiv((uint32_t)k.r0w);
+    k.div_r1w = make_fastdiv((uint32_t)k.r1w);
+    k.div_tw = make_fastdiv((uint32_t)k.TW);
+    k.div_cvgs = make_fastdiv((uint32_t)k.cvgs);
+    k.div_tiles_w = make_fastdiv((uint32_t)k.tiles_w);
+    k.div_tiles_h = make_fastdiv((uint32_t)k.tiles_h);
+    q.variant = BS_VARIANT_NHWC_TILE;
+    q.threads = 256;
+    q.grid = q.in_shape[0] * (int64_t)k.tiles_h * k.tiles_w * k.cvgs;
+    if (q.grid > 0x7fffffffll) return BS_ERR_UNSUPPORTED;
+    q.tile_rows = bth;
+    q.tile_cols = btw;
+    q.planes_per_group = bcvb * vec;
+    q.redundancy = (double)k.tiles_h * k.tiles_w * r0[0] * r0[1] / ((double)k.H * k.W);
+    q.n_levels = 2;
     return BS_OK;
 }
 
@@ -1199,9 +1314,29 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
     std::vector<SeqDraft> drafts;
     const bool nhwc = o.layout == BS_LAYOUT_NHWC;
     if (nhwc) {
-        // channels-last kernels take one step (one pooling operation) per sequence
+        // channels-last kernels take one step (one pooling operation) per sequence, or two that
+        // the tile kernel exists for: neighbouring steps are paired from the front
         const bs_status fs = fill(1, drafts);
         if (fs != BS_OK) return fs;
+        if (!per_layer && o.max_steps_per_sequence != 1) {
+            std::vector<SeqDraft> paired;
+            for (size_t i = 0; i < drafts.size(); ++i) {
+                if (i + 1 < drafts.size()) {
+                    Sequence trial;
+                    trial.in_shape[0] = s->in_shape[0];
+                    trial.in_shape[1] = s->in_shape[1];
+                    const SeqDraft both{drafts[i].first_step, 2};
+                    range_ops(both, trial.first_op, trial.n_ops);
+                    if (plan_nhwc_tile2(s, trial, o) == BS_OK) {
+                        paired.push_back(both);
+                        ++i;
+                        continue;
+                    }
+                }
+                paired.push_back(drafts[i]);
+            }
+            drafts.swap(paired);
+        }
     } else if (o.max_steps_per_sequence > 0 || per_layer || o.force_variant != BS_VARIANT_AUTO) {
         const bs_status fs = fill(o.max_steps_per_sequence, drafts);
         if (fs != BS_OK) return fs;
@@ -1242,7 +1377,7 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
         q.n_levels = pools;
         bs_status st = BS_OK;
         if (nhwc) {
-            st = plan_nhwc(s, q);
+            st = q.n_steps == 2 ? plan_nhwc_tile2(s, q, o) : plan_nhwc(s, q);
         } else if (pools == 0) {
             plan_stream(s, q);
         } else if (direct_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {
@@ -1286,7 +1421,7 @@ bs_status bs_stack_plan(bs_stack *stack, const bs_plan_options *opts)
     if (o.threads_per_group != 0 &&
         (o.threads_per_group < 64 || o.threads_per_group > 512 || o.threads_per_group % 64 != 0))
         return BS_ERR_PARAM;
-    if (o.force_variant < 0 || o.force_variant > BS_VARIANT_PLANE_POOL) return BS_ERR_PARAM;
+    if (o.force_variant < 0 || o.force_variant > BS_VARIANT_PLANE_POOL) return BS_ERR_PARAM;  // the forceable families
     if (o.max_lds_bytes > 64 * 1024) return BS_ERR_PARAM;
     if (o.jit < -1 || o.jit > 1) return BS_ERR_PARAM;
     if (o.layout != BS_LAYOUT_NCHW && o.layout != BS_LAYOUT_NHWC) return BS_ERR_PARAM;

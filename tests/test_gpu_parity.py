@@ -764,8 +764,11 @@ def _check_nhwc(layers, x, res, dtype, label, **opts):
     assert len(idx) == len(ref_idx)
     for a, b in zip(idx, ref_idx):
         assert np.array_equal(a.cpu().numpy(), b), label
-    assert info["n_sequences"] == info["n_steps"]
-    assert all(q["variant_name"] in ("nhwc_stream", "nhwc_pool") for q in info["sequences"])
+    names = [q["variant_name"] for q in info["sequences"]]
+    assert all(v in ("nhwc_stream", "nhwc_pool", "nhwc_tile") for v in names)
+    assert sum(2 if v == "nhwc_tile" else 1 for v in names) == info["n_steps"]
+    if opts.get("max_steps_per_sequence") == 1 or opts.get("breadth_first"):
+        assert "nhwc_tile" not in names
     return info
 
 
@@ -810,6 +813,56 @@ def test_channels_last_plans_match_the_oracle(shape, dtype):
 def test_channels_last_configs_reduced_batch(name, dtype):
     layers, x, res = _shrunk(name, dtype, batch=2)
     _check_nhwc(layers, x, res, dtype, name)
+    _check_nhwc(layers, x, res, dtype, name + "/step-by-step", max_steps_per_sequence=1)
+
+
+def _tile_stacks(c):
+    """Two pooling steps the channels-last tile kernel exists for: every pair of its windows
+    (3 x 3 stride 1 and 2, 2 x 2 stride 2), both pooling kinds on either level, lists in front,
+    between and behind (residual operands at each plane size), every divisor rule, ceil mode."""
+    win = {"3s1": (3, 1, 1), "3s2": (3, 2, 1), "2s2": (2, 2, 0)}
+    stacks = {}
+    for a, (k1, s1, p1) in win.items():
+        for b, (k2, s2, p2) in win.items():
+            stacks[f"avg{a}_max{b}_idx"] = [wl.bn_params(c, 170), wl.relu(), wl.avgpool(k1, s1, p1, True),
+                                            wl.maxpool(k2, s2, p2, True), wl.bn_params(c, 171), wl.relu()]
+            stacks[f"max{a}_avg{b}"] = [wl.maxpool(k1, s1, p1), wl.bn_params(c, 172), wl.add(), wl.relu(),
+                                        wl.avgpool(k2, s2, p2, False), wl.add()]
+    stacks["max_max_lists_move"] = [wl.bn_params(c, 173), wl.relu(), wl.maxpool(3, 2, 1), wl.relu(), wl.bn_params(c, 174),
+                                    wl.maxpool(3, 1, 1), wl.leaky_relu(0.2)]
+    stacks["add_first"] = [wl.add(), wl.bn_params(c, 175), wl.maxpool(3, 1, 1), wl.clamp(-0.5, 0.75), wl.maxpool(2, 2, 0, True)]
+    stacks["avg_avg_ceil"] = [wl.avgpool(3, 2, 1, True, True), wl.bn_params(c, 176), wl.avgpool(2, 2, 0, False, True)]
+    stacks["max_ceil_max_ceil"] = [wl.relu(), wl.maxpool(3, 2, 0, False, True), wl.maxpool(3, 2, 1, True, True)]
+    stacks["no_padding"] = [wl.bn_params(c, 177), wl.avgpool(3, 1, 0), wl.relu(), wl.maxpool(3, 2, 0, True)]
+    return stacks
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 13, 11), (1, 16, 9, 16), (2, 24, 12, 10), (1, 8, 57, 31), (3, 32, 7, 7), (1, 128, 6, 5)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_channels_last_two_pools_in_one_kernel(shape, dtype):
+    """The tile kernel against the oracle: the planner's own tile, one output per work-group,
+    ragged tiles with one channel vector per work-group, and a tile larger than the plane."""
+    vec = 4 if dtype == "f32" else 8
+    ran = 0
+    for name, layers in _tile_stacks(shape[1]).items():
+        cur, ok = shape, True
+        for l in layers:
+            if l["kind"] in ("maxpool", "avgpool") and (cur[2] + 2 * l["p"][0] < l["k"][0] or cur[3] + 2 * l["p"][1] < l["k"][1]):
+                ok = False
+                break
+            cur = wl.output_shape([l], cur)
+            ok = ok and cur[2] >= 1 and cur[3] >= 1
+        if not ok:
+            continue
+        x = wl.activation(shape, 178, dtype)
+        x[:, :, ::3, ::2] = 0.0  # ties for the maximum and for its index
+        res = [wl.activation(sh, 179 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
+        for opts in ({}, dict(tile_rows=1, tile_cols=1), dict(tile_rows=3, tile_cols=2, planes_per_group=vec),
+                     dict(tile_rows=16, tile_cols=16, planes_per_group=vec)):
+            info = _check_nhwc(layers, x, res, dtype, f"tile/{name}{shape}", **opts)
+            assert [q["variant_name"] for q in info["sequences"]] == ["nhwc_tile"], name
+        ran += 1
+    assert ran >= 10
 
 
 def _premax_stacks(c):
@@ -893,7 +946,8 @@ def test_channels_last_channel_slices(shape, dtype):
 
 
 @pytest.mark.parametrize("name,dtype", [("vgg_a", "f32"), ("resnet_stem", "bf16"), ("resnet_tail", "f16"),
-                                        ("densenet_trans", "f32"), ("halo_stress", "f16")])
+                                        ("densenet_trans", "f32"), ("halo_stress", "f16"), ("halo_stress", "f32"),
+                                        ("halo_stress", "bf16")])
 def test_channels_last_configs_full_size(name, dtype):
     """Whole tensors at the benchmark sizes with channels-last plans, as `bench.py --nhwc` times them."""
     layers, x, res = wl.inputs_for(name, 0, dtype, indices=False)

@@ -244,22 +244,51 @@ def test_capacity_splits_keep_every_operation():
     assert sum(q["n_layers"] for q in info["sequences"]) == 50
 
 
-def test_channels_last_plans_take_one_step_per_sequence():
-    """Host-only channels-last plans: a sequence per step, the two channels-last kernel families,
-    workspace between the sequences; options that belong to the NCHW kernels are refused."""
+def test_channels_last_plans_take_one_or_two_steps_per_sequence():
+    """Host-only channels-last plans: a sequence per step (or per pair of steps the tile kernel
+    exists for), the channels-last kernel families, workspace between the sequences; options
+    that belong to the NCHW kernels are refused."""
     for name in ("vgg_a", "resnet_stem", "resnet_tail", "densenet_trans", "halo_stress"):
         layers, shape, dtypes = wl.build(name)
         for dtype in dtypes:
-            st = bs.Stack(layers, shape, dtype).plan(host_only=1, layout=bs.BS_LAYOUT_NHWC)
+            pools = sum(1 for l in layers if l["kind"] in ("maxpool", "avgpool"))
+            st = bs.Stack(layers, shape, dtype).plan(host_only=1, layout=bs.BS_LAYOUT_NHWC, max_steps_per_sequence=1)
             info = st.info()
             assert info["n_sequences"] == info["n_steps"]
-            pools = sum(1 for l in layers if l["kind"] in ("maxpool", "avgpool"))
             names = [q["variant_name"] for q in info["sequences"]]
             assert names == (["nhwc_pool"] * pools if pools else ["nhwc_stream"])
             assert (info["workspace_bytes"] > 0) == (pools > 1)
             for q in info["sequences"]:
                 assert q["run_time_build"] == 0 and q["lds_bytes"] == 0 and q["grid"] >= 1
             st.close()
+            st = bs.Stack(layers, shape, dtype).plan(host_only=1, layout=bs.BS_LAYOUT_NHWC)
+            info = st.info()
+            names = [q["variant_name"] for q in info["sequences"]]
+            assert names == (["nhwc_tile"] if pools == 2 else ["nhwc_pool"] * pools if pools else ["nhwc_stream"])
+            assert info["workspace_bytes"] == 0
+            for q in info["sequences"]:
+                if q["variant_name"] != "nhwc_tile":
+                    continue
+                # both rectangles of the tile, one 16-byte vector per cell and channel vector, within the LDS limit
+                th, tw, cv = q["tile_rows"], q["tile_cols"], q["planes_per_group"] // (4 if dtype == "f32" else 8)
+                r1 = ((th - 1) * 2 + 3, (tw - 1) * 2 + 3)   # max pool 3 x 3 stride 2 on top
+                r0 = (r1[0] + 2, r1[1] + 2)                 # average pool 3 x 3 stride 1 under it
+                assert q["lds_bytes"] == (r0[0] * r0[1] + r1[0] * r1[1]) * cv * 16 <= 64 * 1024
+                assert q["n_steps"] == 2 and q["n_levels"] == 2 and q["threads_per_group"] == 256
+                assert q["grid"] == shape[0] * -(-28 // th) * -(-28 // tw) * (shape[1] * (4 if dtype == "f32" else 2) // 16 // cv)
+                assert 1.0 < q["redundancy"] < 2.0
+            st.close()
+    # pairs are taken from the front; windows outside the tile kernel's table, first pools with
+    # an index output and channel counts that give no 128-bit vectors stay one step per sequence
+    three = [wl.maxpool(3, 2, 1), wl.relu(), wl.avgpool(2, 2, 0), wl.maxpool(3, 1, 1, True)]
+    for layers, shape, want in ((three, (1, 8, 32, 32), ["nhwc_tile", "nhwc_pool"]),
+                                ([wl.maxpool(5, 1, 2), wl.avgpool(3, 1, 1)], (1, 8, 16, 16), ["nhwc_pool"] * 2),
+                                ([wl.maxpool(3, 1, 1, True), wl.avgpool(3, 1, 1)], (1, 8, 16, 16), ["nhwc_pool"] * 2),
+                                ([wl.maxpool(3, 1, 1), wl.avgpool(3, 1, 1)], (1, 6, 16, 16), ["nhwc_pool"] * 2),
+                                ([wl.maxpool(3, 1, 1), wl.maxpool(3, 1, 1, True)], (1, 8, 16, 16), ["nhwc_tile"])):
+        st = bs.Stack(layers, shape, "f32").plan(host_only=1, layout=bs.BS_LAYOUT_NHWC)
+        assert [q["variant_name"] for q in st.info()["sequences"]] == want
+        st.close()
     h = bs.bs_stack_create([wl.relu()], (1, 4, 8, 8), "f32")
     try:
         for bad in (dict(layout=2), dict(layout=-1), dict(layout=1, force_variant=bs.BS_VARIANT_STREAM)):
