@@ -171,12 +171,21 @@ typedef enum bs_layout {
  *   layout                  bs_layout of the input, the residual operands, the output and the
  *                           index outputs.  BS_LAYOUT_NHWC plans run one step (one pooling
  *                           operation with the element-wise operations around it) per
- *                           sequence and use their own two kernel families; force_variant
- *                           must be automatic, tile options and jit are ignored.  A channel
- *                           slice of a channels-last tensor skips the other channels in
- *                           every pixel: bs_stack_run_strided takes its batch stride, which
- *                           must be H * W times the larger tensor's channel count.  Index outputs
- *                           hold the same values (ih * W + iw) in channels-last order.
+ *                           sequence, or two neighbouring steps in one BS_VARIANT_NHWC_TILE
+ *                           sequence when both windows are 3 x 3 (stride 1 or 2) or 2 x 2
+ *                           (stride 2), the first pool has no index output and C is a
+ *                           multiple of the 128-bit vector (never with
+ *                           max_steps_per_sequence = 1 or breadth_first); force_variant must
+ *                           be automatic and jit is ignored.  For that variant tile_rows and
+ *                           tile_cols are upper bounds of the output tile and
+ *                           planes_per_group the channels per work-group; its work-groups
+ *                           walk runs of tiles, and the grid reported by bs_stack_sequence_info
+ *                           is an upper bound (at most as many groups are launched as the
+ *                           device holds at once).  A channel slice of a channels-last tensor
+ *                           skips the other channels in every pixel: bs_stack_run_strided
+ *                           takes its batch stride, which must be H * W times the larger
+ *                           tensor's channel count.  Index outputs hold the same values
+ *                           (ih * W + iw) in channels-last order.
  *   lane_exchange           sliding-window (BS_VARIANT_POOL_ROWS) sequences on planes whose rows fit one
  *                           wave as 128-bit column blocks (at most 64 of them): 0 = the lanes pass
  *                           their edge columns to their neighbours inside the wave (each input

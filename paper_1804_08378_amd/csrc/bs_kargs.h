@@ -215,9 +215,11 @@ struct NhwcK {
                       // div_wo then divides by the work-groups per image
 };
 
-// Channels-last sequence of two pooling steps in one kernel (bs_nhwc_tile.hip): a work-group owns
-// TH x TW output pixels of one image and `cvb` consecutive channel vectors, and keeps the rectangles
-// of the input plane (r0h x r0w cells) and of the plane between the pools (r1h x r1w) under them in LDS.
+// Channels-last sequence of two pooling steps in one kernel (bs_nhwc_tile.hip): a tile is TH x TW
+// output pixels of one image and `cvb` consecutive channel vectors; a work-group keeps the rectangles
+// of the input plane (r0h x r0w cells) and of the plane between the pools (r1h x r1w) under a tile in
+// LDS and walks a run of consecutive tiles.
+constexpr int K_TILE_MAX_BN = 3 * K_MAX_EW;
 struct NhwcTile2K {
     const void *in;
     void *out;
@@ -230,8 +232,14 @@ struct NhwcTile2K {
     int32_t C, H, W, H1, W1, Ho, Wo;
     int32_t TH, TW, r0h, r0w, r1h, r1w;
     int32_t cvb, pl;             // channel vectors per work-group; pixel lanes = threads / cvb
-    int32_t cvgs, tiles_h, tiles_w;  // work-groups per tile (C / vec / cvb), tiles per image
-    FastDiv div_cvb, div_r0w, div_r1w, div_tw, div_cvgs, div_tiles_w, div_tiles_h;
+    int32_t cvgs, tiles_h, tiles_w;  // channel-vector groups (C / vec / cvb), tiles per image
+    uint32_t total_tiles;        // cvgs * N * tiles_h * tiles_w, numbered in that order
+    uint32_t lds1_off, par_off;  // first LDS vector of the second rectangle, of the staged BatchNorm parameters
+    int32_t n_bn;                // BatchNorm operations of the three lists, in order
+    int32_t bn_base[3];          // how many of them precede the lists pre, mid, post
+    int32_t bn_arg[K_TILE_MAX_BN];   // where their scale[] starts in the parameter table (shift[] follows)
+    FastDiv div_cvb, div_r0w, div_n, div_tiles_w, div_tiles_h;
+    FastDiv div_bw1, div_bw2;    // by the blocks per rectangle row of the two pooling levels
     uint32_t in_xp, out_xp;      // as in NhwcK
 };
 

@@ -23,10 +23,12 @@ BS_DEV void load_params(const float *__restrict__ params, uint32_t off, float (&
 }
 
 // Apply an element-wise list to U register vectors that all hold channels c0 .. c0 + VEC - 1.
-//   off[u]  element offset of vector u in this level's tensors (residual loads)
+//   off[u]  element offset of vector u in this level's tensors (residual loads), counted from
+//           element res_base (the same for all lanes)
 template <int DT, int VEC, int U>
 BS_DEV void apply_ew_nhwc(float (&x)[U][VEC], uint32_t c0, const uint32_t (&off)[U], const EwOp *ew,
-                          int32_t n_ew, const float *__restrict__ params, int32_t C, const void *const *res)
+                          int32_t n_ew, const float *__restrict__ params, int32_t C, const void *const *res,
+                          uint32_t res_base = 0)
 {
 #pragma clang loop unroll(disable)
     for (int32_t j = 0; j < n_ew; ++j) {
@@ -61,7 +63,7 @@ BS_DEV void apply_ew_nhwc(float (&x)[U][VEC], uint32_t c0, const uint32_t (&off)
             const void *rp = res[arg];
             Raw<DT, VEC> rr[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) rr[u] = load_raw<DT, VEC, true>(rp, off[u]);
+            for (int u = 0; u < U; ++u) rr[u] = load_raw<DT, VEC, true>(rp, off[u] + res_base);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float r[VEC];

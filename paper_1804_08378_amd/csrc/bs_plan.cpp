@@ -542,7 +542,7 @@ static bs_status plan_nhwc(const bs_stack *s, Sequence &q)
 
 // Channels-last sequence of two pooling steps: one kernel, tiles of both planes in LDS.
 // BS_ERR_UNSUPPORTED when the pair is not one the kernel exists for (the steps then run one by one).
-static bs_status plan_nhwc_tile2(const bs_stack *s, Sequence &q, const bs_plan_options &o)
+static bs_status plan_nhwc_tile2(const bs_stack *s, Sequence &q, const bs_plan_options &o, const Limits &lim)
 {
     NhwcTile2K &k = q.nhwc2;
     k = NhwcTile2K{};
@@ -571,6 +571,9 @@ static bs_status plan_nhwc_tile2(const bs_stack *s, Sequence &q, const bs_plan_o
         }
     }
     if (!nhwc_tile2_supported(k.pool1, k.pool2)) return BS_ERR_UNSUPPORTED;
+    if (!nhwc_tile2_sizes_ok(k.H, k.W, C, 0, s->dtype) || !nhwc_tile2_sizes_ok(k.H1, k.W1, C, 0, s->dtype) ||
+        !nhwc_tile2_sizes_ok(k.Ho, k.Wo, C, 0, s->dtype))
+        return BS_ERR_UNSUPPORTED;
     k.C = C;
     // maximum first (see plan_nhwc): a list in front of a max pool that commutes with the maximum
     // runs once per pooled value, behind the pool
@@ -589,55 +592,71 @@ static bs_status plan_nhwc_tile2(const bs_stack *s, Sequence &q, const bs_plan_o
         commutes_with_max(s, k.mid, k.n_mid, C))
         move_behind(k.mid, k.n_mid, k.post, k.n_post);
 
-    // Tile and channel group.  Candidates: channel groups that divide the pixel's vectors (at
-    // most 16 per work-group), every tile up to 16 x 16 outputs whose two rectangles fit the LDS
-    // budget.  Cost of a candidate = cells a work-group touches per image at each level (input
-    // cells weigh most: a global load and the leading element-wise list), scaled up when the
-    // group's run of channels is shorter than a 128-byte line or when fewer than three
-    // work-groups fit a compute unit's LDS.
+    // BatchNorm operations of the three lists, in order: the kernel stages their parameters in LDS
+    {
+        const EwOp *lists[3] = {k.pre, k.mid, k.post};
+        const int32_t counts[3] = {k.n_pre, k.n_mid, k.n_post};
+        for (int l = 0; l < 3; ++l) {
+            k.bn_base[l] = k.n_bn;
+            for (int32_t j = 0; j < counts[l]; ++j)
+                if (lists[l][j].kind == OP_BN) k.bn_arg[k.n_bn++] = lists[l][j].arg;
+        }
+    }
+    // Tile and channel group.  A lane has a fixed share of a tile (a few input cells, one block
+    // per pooling level), so every tile takes about the same time whatever its size: the best
+    // tile is the one that covers the output plane with the fewest work-group passes.
+    // Candidates: channel groups that divide the pixel's vectors (at most 16 per work-group)
+    // and tiles that leave no lane more than its share and fit the LDS budget; tile options
+    // are upper bounds.  Small penalties for channel runs shorter than a 128-byte line and
+    // for tiles that leave many lanes idle break ties.
     const int32_t cvn = C / vec;
-    const uint64_t lds_cap = std::min<uint64_t>(64 * 1024, std::max<uint64_t>(o.max_lds_bytes ? o.max_lds_bytes : 64 * 1024, 1));
+    const uint64_t lds_cap = std::min<uint64_t>(64 * 1024, o.max_lds_bytes ? o.max_lds_bytes : 64 * 1024);
     double best = 0.0;
     int32_t bth = 0, btw = 0, bcvb = 0;
     for (int32_t cvb = std::min(cvn, 16); cvb >= 1; --cvb) {
         if (cvn % cvb != 0) continue;
         if (o.planes_per_group > 0 && cvb * vec != o.planes_per_group) continue;
-        for (int32_t th = 1; th <= std::min(16, k.Ho); ++th)
-            for (int32_t tw = 1; tw <= std::min(16, k.Wo); ++tw) {
-                if (o.tile_rows > 0 && th != std::min(o.tile_rows, k.Ho)) continue;
-                if (o.tile_cols > 0 && tw != std::min(o.tile_cols, k.Wo)) continue;
-                int32_t r0[2], r1[2];
-                const uint64_t lds = nhwc_tile2_lds(k.pool1, k.pool2, th, tw, cvb, r0, r1);
-                if (lds > lds_cap) continue;
+        const int32_t pl = 256 / cvb;
+        for (int32_t th = 1; th <= std::min(o.tile_rows > 0 ? o.tile_rows : 32, k.Ho); ++th)
+            for (int32_t tw = 1; tw <= std::min(o.tile_cols > 0 ? o.tile_cols : 32, k.Wo); ++tw) {
+                if (!nhwc_tile2_fits(k.pool1, k.pool2, th, tw, pl)) continue;
+                if (nhwc_tile2_lds(k.pool1, k.pool2, th, tw, cvb, k.n_bn, vec) > lds_cap) continue;
                 const int64_t tiles = (int64_t)((k.Ho + th - 1) / th) * ((k.Wo + tw - 1) / tw);
-                const int32_t pl = 256 / cvb;
-                auto passes = [&](int64_t cells) { return (double)((cells + pl - 1) / pl) * pl; };  // lanes idle in the last pass
-                double cost = (double)tiles * (3.0 * passes((int64_t)r0[0] * r0[1]) + 2.0 * passes((int64_t)r1[0] * r1[1]) + 2.0 * passes((int64_t)th * tw));
-                if ((uint64_t)cvb * 16 < 128) cost *= 1.0 + 0.1 * (128.0 / (cvb * 16.0) - 1.0);
-                const int32_t resident = (int32_t)std::min<uint64_t>(8, (160 * 1024) / std::max<uint64_t>(lds, 1));
-                if (resident < 3) cost *= 1.0 + 0.15 * (3 - resident);
+                double cost = (double)tiles * (cvn / cvb);
+                if ((uint64_t)cvb * 16 < 128) cost *= 1.0 + 0.05 * (128.0 / (cvb * 16.0) - 1.0);
+                cost *= 1.0 + 0.02 * (1.0 - (double)th * tw / pl);
                 if (bth == 0 || cost < best) { best = cost; bth = th; btw = tw; bcvb = cvb; }
             }
     }
     if (bth == 0) return BS_ERR_UNSUPPORTED;
-    int32_t r0[2], r1[2];
-    q.lds_bytes = nhwc_tile2_lds(k.pool1, k.pool2, bth, btw, bcvb, r0, r1);
+    int32_t r0[2], r1[2], cells[2], bw[2];
+    nhwc_tile2_shape(k.pool1, k.pool2, bth, btw, r0, r1, cells, bw);
+    q.lds_bytes = nhwc_tile2_lds(k.pool1, k.pool2, bth, btw, bcvb, k.n_bn, vec);
     k.TH = bth; k.TW = btw; k.cvb = bcvb; k.pl = 256 / bcvb;
     k.r0h = r0[0]; k.r0w = r0[1]; k.r1h = r1[0]; k.r1w = r1[1];
+    k.lds1_off = (uint32_t)(cells[0] * bcvb);
+    k.par_off = (uint32_t)((cells[0] + cells[1]) * bcvb);
     k.cvgs = cvn / bcvb;
     k.tiles_h = (k.Ho + bth - 1) / bth;
     k.tiles_w = (k.Wo + btw - 1) / btw;
+    const int64_t total = q.in_shape[0] * (int64_t)k.tiles_h * k.tiles_w * k.cvgs;
+    if (total > 0x7fffffffll) return BS_ERR_UNSUPPORTED;
+    k.total_tiles = (uint32_t)total;
     k.div_cvb = make_fastdiv((uint32_t)k.cvb);
     k.div_r0w = make_fastdiv((uint32_t)k.r0w);
-    k.div_r1w = make_fastdiv((uint32_t)k.r1w);
-    k.div_tw = make_fastdiv((uint32_t)k.TW);
-    k.div_cvgs = make_fastdiv((uint32_t)k.cvgs);
+    k.div_bw1 = make_fastdiv((uint32_t)bw[0]);
+    k.div_bw2 = make_fastdiv((uint32_t)bw[1]);
+    k.div_n = make_fastdiv((uint32_t)q.in_shape[0]);
     k.div_tiles_w = make_fastdiv((uint32_t)k.tiles_w);
     k.div_tiles_h = make_fastdiv((uint32_t)k.tiles_h);
     q.variant = BS_VARIANT_NHWC_TILE;
     q.threads = 256;
-    q.grid = q.in_shape[0] * (int64_t)k.tiles_h * k.tiles_w * k.cvgs;
-    if (q.grid > 0x7fffffffll) return BS_ERR_UNSUPPORTED;
+    // work-groups: at most as many as the chip could hold at once by LDS, each with a run of
+    // consecutive tiles (the launcher lowers the count to what the kernel's registers allow)
+    {
+        const int32_t resident = (int32_t)std::min<uint64_t>(8, (160 * 1024) / std::max<uint64_t>(q.lds_bytes, 1));
+        q.grid = std::min<int64_t>(total, (int64_t)std::max(1, lim.num_cus) * std::max(1, resident));
+    }
     q.tile_rows = bth;
     q.tile_cols = btw;
     q.planes_per_group = bcvb * vec;
@@ -1327,7 +1346,7 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
                     trial.in_shape[1] = s->in_shape[1];
                     const SeqDraft both{drafts[i].first_step, 2};
                     range_ops(both, trial.first_op, trial.n_ops);
-                    if (plan_nhwc_tile2(s, trial, o) == BS_OK) {
+                    if (plan_nhwc_tile2(s, trial, o, lim) == BS_OK) {
                         paired.push_back(both);
                         ++i;
                         continue;
@@ -1377,7 +1396,7 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
         q.n_levels = pools;
         bs_status st = BS_OK;
         if (nhwc) {
-            st = q.n_steps == 2 ? plan_nhwc_tile2(s, q, o) : plan_nhwc(s, q);
+            st = q.n_steps == 2 ? plan_nhwc_tile2(s, q, o, lim) : plan_nhwc(s, q);
         } else if (pools == 0) {
             plan_stream(s, q);
         } else if (direct_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {

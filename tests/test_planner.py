@@ -269,13 +269,21 @@ def test_channels_last_plans_take_one_or_two_steps_per_sequence():
             for q in info["sequences"]:
                 if q["variant_name"] != "nhwc_tile":
                     continue
-                # both rectangles of the tile, one 16-byte vector per cell and channel vector, within the LDS limit
-                th, tw, cv = q["tile_rows"], q["tile_cols"], q["planes_per_group"] // (4 if dtype == "f32" else 8)
+                # both rectangles of the tile (each followed by spare rows for blocks that hang over its edge), one
+                # 16-byte vector per cell and channel vector, and the two BatchNorm operations' scale and shift
+                # vectors; a lane holds at most four input cells and one block per pooling level
+                vec = 4 if dtype == "f32" else 8
+                th, tw, cv = q["tile_rows"], q["tile_cols"], q["planes_per_group"] // vec
                 r1 = ((th - 1) * 2 + 3, (tw - 1) * 2 + 3)   # max pool 3 x 3 stride 2 on top
-                r0 = (r1[0] + 2, r1[1] + 2)                 # average pool 3 x 3 stride 1 under it
-                assert q["lds_bytes"] == (r0[0] * r0[1] + r1[0] * r1[1]) * cv * 16 <= 64 * 1024
+                r0 = (r1[0] + 2, r1[1] + 2)                 # average pool 3 x 3 stride 1 under it (2 x 2 blocks)
+                cells = (r0[0] + 2) * r0[1] + (r1[0] + 1) * r1[1]
+                assert q["lds_bytes"] == cells * cv * 16 + 2 * 2 * cv * vec * 4 <= 64 * 1024
+                lanes = 256 // cv
+                assert r0[0] * r0[1] <= 4 * lanes and -(-r1[0] // 2) * -(-r1[1] // 2) <= lanes and th * tw <= lanes
                 assert q["n_steps"] == 2 and q["n_levels"] == 2 and q["threads_per_group"] == 256
-                assert q["grid"] == shape[0] * -(-28 // th) * -(-28 // tw) * (shape[1] * (4 if dtype == "f32" else 2) // 16 // cv)
+                # work-groups walk runs of tiles: no more groups than 256 compute units hold at once by LDS
+                tiles = shape[0] * -(-28 // th) * -(-28 // tw) * (shape[1] // vec // cv)
+                assert q["grid"] == min(tiles, 256 * min(8, 160 * 1024 // q["lds_bytes"]))
                 assert 1.0 < q["redundancy"] < 2.0
             st.close()
     # pairs are taken from the front; windows outside the tile kernel's table, first pools with
