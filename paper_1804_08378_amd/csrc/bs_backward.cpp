@@ -188,6 +188,26 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
                 }
                 lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 2 : 1);
                 g.k.div_wv = make_fastdiv((uint32_t)(g.k.flat ? 1 : g.k.W / g.vec));
+                // overlapping 3 x 3 max windows on rows that fit one wave: the kernel that finds the picks itself
+                if (p.kind == OP_MAXPOOL && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && p.sh == p.sw &&
+                    (p.sh == 1 || p.sh == 2) && g.vec == full && g.k.W / full <= 64 && g.k.Wo * p.sw == g.k.W &&
+                    g.k.Ho == (g.k.H + 2 - 3) / p.sh + 1 && stack->opts.lane_exchange >= 0) {
+                    BwdK &k = g.k;
+                    k.own_picks = 1;
+                    k.cbs = k.W / full;
+                    k.spw = 64 / k.cbs;
+                    // window rows per chunk: a chunk also visits the window rows just above and below it
+                    const int64_t planes = g.in_shape[0] * g.in_shape[1];
+                    const int32_t rows = (k.H + p.sh - 1) / p.sh;  // window rows that cover the plane's rows
+                    int32_t rc = std::min(K_BWD_MAXROWS_RC, rows);
+                    k.chunks = (rows + rc - 1) / rc;
+                    k.rc = (rows + k.chunks - 1) / k.chunks;
+                    k.chunks = (rows + k.rc - 1) / k.rc;
+                    k.units = (uint32_t)(planes * k.chunks);
+                    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+                    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+                    lanes = (uint64_t)k.units * (uint64_t)k.cbs;
+                }
             }
             if (lanes > 0x7fffffffull) { st = BS_ERR_UNSUPPORTED; break; }
             g.k.total = (uint32_t)lanes;
@@ -195,7 +215,8 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
             g.k.div_c = make_fastdiv((uint32_t)g.k.C);
             g.threads = 256;
             g.grid = (int64_t)((lanes + 255) / 256);
-            const bool is_max = p.kind == OP_MAXPOOL && !g.k.direct;  // recorded picks needed
+            if (g.k.own_picks) g.grid = ((int64_t)g.k.units + 4 * g.k.spw - 1) / (4 * g.k.spw);  // whole segments per wave
+            const bool is_max = p.kind == OP_MAXPOOL && !g.k.direct && !g.k.own_picks;  // recorded picks needed
             // the buffers are sized by these shapes: a stage must end where the next one begins
             const int64_t *next = j + 1 < S ? plan->stages[j + 1].in_shape : stack->out_shape;
             if (std::memcmp(g.out_shape, next, sizeof g.out_shape) != 0) { st = BS_ERR_SHAPE; break; }
@@ -301,7 +322,7 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         void *out = j + 1 < S ? ws + plan.stages[j + 1].a_off : ws + plan.last_out_off;
         const void *res[K_MAX_RES] = {nullptr, nullptr, nullptr, nullptr};
         for (int32_t r = 0; r < g.n_res; ++r) res[r] = residuals[g.res_map[r]];
-        const bool picks = g.k.pool.kind == OP_MAXPOOL && !g.k.direct;
+        const bool picks = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.own_picks;
         int32_t *idx[1] = {picks ? reinterpret_cast<int32_t *>(ws + g.idx_off) : nullptr};
         const bs_status st = bs_stack_run(g.forward, a, res, out, g.forward->n_idx > 0 ? idx : nullptr,
                                           ws + plan.fwd_ws_off, plan.fwd_ws_bytes, stream);
@@ -314,7 +335,7 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         k.a = j == 0 ? in : ws + g.a_off;
         k.g_out = j + 1 == S ? grad_out : ws + plan.stages[j + 1].g_off;
         k.g_in = j == 0 ? grad_in : ws + g.g_off;
-        k.idx = g.k.pool.kind == OP_MAXPOOL && !g.k.direct ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
+        k.idx = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.own_picks ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
         if (k.idx && j + 1 == S && kept(g)) k.idx = kept(g);
         k.params = stack->dev_params;
         bool wanted = k.g_in != nullptr;

@@ -18,7 +18,7 @@
 //   3. grad_in = that gradient * t, grad_residual[n] = that gradient * r[n], rounded once.
 // Traffic: the stage input and the gradients in and out move once; the upstream gradient and
 // the picks of overlapping windows are re-read from cache.
-#include "bs_device.h"
+#include "bs_xrows_device.h"
 #include "bs_internal.h"
 
 namespace bs {
@@ -497,6 +497,151 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 }
 
 // =============================================================================
+// bwd_maxrows_kernel: a stage whose max pooling has overlapping 3 x 3 windows (padding 1, stride
+// S = 1 or 2; BatchNorm -> ReLU -> MaxPool of the ResNet stem) on planes whose rows fit one wave.
+// No recorded picks and no recomputation pass: the stage input, the upstream gradient and the
+// gradient with respect to the input move once.
+//
+// The lanes of a plane's row sit side by side in one wave (a lane owns one column block of VEC
+// cells, as in the forward sliding-window kernels) and walk down a chunk of rows.  A lane keeps
+// the three input rows of the current window row in registers: the values after the element-wise
+// list (with its neighbours' edge columns, one lane-shift each), the list's derivative factors,
+// and the gradient sums collected so far.  Per window row it reads S new input rows and its VO =
+// VEC / S upstream gradients, finds each of its windows' first maximum (row-major, as the forward
+// kernels do), adds the window's gradient to the picked cell -- a pick in a neighbour's column
+// travels there by one lane-shift -- and writes the S rows no later window touches.  A cell sums
+// its windows in row-major window order (earlier window rows first; within a row the left
+// neighbour's window, the lane's own windows from left to right, the right neighbour's window):
+// no atomics, the same bits on every run.
+//
+// Chunks overlap: the rows a chunk writes are [rc * S * chunk, rc * S * (chunk + 1)) (to the end
+// of the plane for the last one); it also visits the window row above and the one below, whose
+// other rows belong to the neighbouring chunks.  Every lane of a wave runs the same number of
+// iterations whether or not its windows exist.
+// =============================================================================
+template <int DT, int VEC, int S, int NR>
+__global__ __launch_bounds__(256) void bwd_maxrows_kernel(const BwdK k)
+{
+    constexpr int K = 3, P = 1, VO = VEC / S, NL = P, NX = K - S - P, CW = NL + VEC + NX;
+    constexpr int KEEP = K - S;  // rows two consecutive window rows share
+    static_assert(VEC % S == 0 && (S == 1 || S == 2), "strides of the compiled windows");
+    const XLane L = xrows_lane(k);
+    const int32_t col0 = L.j * VEC;
+    const bool has_left = L.j > 0, has_right = L.j + 1 < k.cbs;
+    const uint32_t plane_off = L.plane * (uint32_t)(k.H * k.W), oplane = L.plane * (uint32_t)(k.Ho * k.Wo);
+    // rows this chunk writes
+    const int32_t r_lo = L.chunk * k.rc * S, r_hi = L.chunk + 1 == k.chunks ? k.H : min(r_lo + k.rc * S, k.H);
+    // window rows it visits: the first that holds row r_lo .. the last that holds a row below r_lo + rc * S
+    constexpr int OFIRST = -((K - 1 - P) / S);  // ceil((P - K + 1) / S)
+    constexpr int OEND = (P + S - 1) / S;
+    const int32_t oh_first = L.chunk * k.rc + OFIRST;
+    // the last chunk goes on until every row of the plane is written (rows below the last window get zeros)
+    const int32_t n_iter = max(k.rc, (k.H - (k.chunks - 1) * k.rc * S + S - 1) / S) + OEND - OFIRST;  // the same for every lane
+
+    float y[K][CW], t[K][VEC], r[NR ? NR : 1][K][VEC], s[K][VEC];
+    int32_t adds = 0;
+    // rows [first, first + N) of the plane -> ring slots [slot, slot + N): element-wise list, padding, edge columns
+    auto take_rows = [&](auto n_tag, int slot, int32_t first) {
+        constexpr int N = decltype(n_tag)::value;
+        float xs[N][VEC], ts[N][VEC], rs[NR ? NR : 1][N][VEC];
+        uint32_t offs[N];
+        int32_t cs[N];
+        Raw<DT, VEC> raw[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            offs[j] = plane_off + (uint32_t)(min(max(first + j, 0), k.H - 1) * k.W + col0);  // outside the plane: a safe row, replaced below
+            cs[j] = L.c;
+            raw[j] = load_raw<DT, VEC, true>(k.a, offs[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) unpack<DT, VEC>(raw[j], xs[j]);
+        adds = ew_sweep<DT, VEC, N, false, NR>(k, cs, offs, xs, ts, rs);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const bool ok = first + j >= 0 && first + j < k.H;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                xs[j][e] = ok ? xs[j][e] : -INFINITY;
+                t[slot + j][e] = ts[j][e];
+                s[slot + j][e] = 0.0f;
+#pragma unroll
+                for (int n = 0; n < NR; ++n) r[n][slot + j][e] = rs[n][j][e];
+            }
+            with_neighbours<VEC, NL, NX>(xs[j], y[slot + j], has_left, has_right, -INFINITY);
+        }
+    };
+    if constexpr (KEEP > 0) take_rows(std::integral_constant<int, KEEP>{}, 0, oh_first * S - P);
+
+    for (int32_t it = 0; it < n_iter; ++it) {
+        const int32_t oh = oh_first + it, hA = oh * S - P;
+        take_rows(std::integral_constant<int, S>{}, KEEP, hA + KEEP);
+        // upstream gradients of the lane's windows of this row; windows that do not exist give nothing
+        const bool row_ok = oh >= 0 && oh < k.Ho;
+        float g[VO];
+        unpack<DT, VO>(load_raw<DT, VO>(k.g_out, oplane + (uint32_t)(min(max(oh, 0), k.Ho - 1) * k.Wo + L.j * VO)), g);
+#pragma unroll
+        for (int e = 0; e < VO; ++e) g[e] = row_ok ? g[e] : 0.0f;
+        // first maximum of every window: code = window row * K + window column
+        int32_t pick[VO];
+#pragma unroll
+        for (int e = 0; e < VO; ++e) {
+            float best = -INFINITY;
+            pick[e] = -1;
+#pragma unroll
+            for (int dh = 0; dh < K; ++dh)
+#pragma unroll
+                for (int dw = 0; dw < K; ++dw) {
+                    const float v = y[dh][e * S + dw];
+                    const bool more = v > best;
+                    best = more ? v : best;
+                    pick[e] = more ? dh * K + dw : pick[e];
+                }
+        }
+        // gradients into the picked cells, in the order a cell's windows have in the plane
+#pragma unroll
+        for (int dh = 0; dh < K; ++dh) {
+            // picks in the neighbours' columns: the first window's first column lies in the left lane's block,
+            // the last window's last column (stride 1) in the right lane's
+            const float to_left = pick[0] == dh * K ? g[0] : 0.0f;
+            const float from_right = from_right_lane(to_left);
+            float from_left = 0.0f;
+            if constexpr (NX > 0) {
+                const float to_right = pick[VO - 1] == dh * K + K - 1 ? g[VO - 1] : 0.0f;
+                from_left = from_left_lane(to_right);
+                s[dh][0] += has_left ? from_left : 0.0f;
+            }
+#pragma unroll
+            for (int e = 0; e < VO; ++e)
+#pragma unroll
+                for (int dw = 0; dw < K; ++dw) {
+                    const int col = e * S + dw - NL;  // the window cell's column in the lane's block
+                    if (col >= 0 && col < VEC) s[dh][col] += pick[e] == dh * K + dw ? g[e] : 0.0f;
+                }
+            s[dh][VEC - 1] += has_right ? from_right : 0.0f;
+        }
+        // the S rows no later window row holds are complete
+#pragma unroll
+        for (int d = 0; d < S; ++d) {
+            const int32_t row = hA + d;
+            if (L.live && row >= r_lo && row < r_hi)
+                store_row<DT, VEC, K, NR>(k, d, plane_off + (uint32_t)(row * k.W + col0), adds, s[d], t, r);
+        }
+#pragma unroll
+        for (int d = 0; d < KEEP; ++d) {
+#pragma unroll
+            for (int e = 0; e < CW; ++e) y[d][e] = y[d + S][e];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                t[d][e] = t[d + S][e];
+                s[d][e] = s[d + S][e];
+#pragma unroll
+                for (int n = 0; n < NR; ++n) r[n][d][e] = r[n][d + S][e];
+            }
+        }
+    }
+}
+
+// =============================================================================
 // Channels-last tensors (N, H, W, C in memory).  A lane owns VEC consecutive channels of one
 // pixel: the same three steps as bwd_stage_kernel, with BatchNorm parameters as per-lane
 // vectors and a window's gradient and picks as one vector each (the VEC channels of the output
@@ -733,6 +878,35 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
                (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_c.d != k.C ||
                (int64_t)grid * threads < (int64_t)k.total) {
         return BS_ERR_UNSUPPORTED;
+    }
+    if (k.own_picks) {
+        const PoolK &p = k.pool;
+        // what the kernel assumes: 3 x 3 max windows, padding 1, stride 1 or 2 that divides the row exactly;
+        // a row's column blocks in one wave; chunks that cover the plane
+        if (k.direct || p.kind != OP_MAXPOOL || p.kh != 3 || p.kw != 3 || p.ph != 1 || p.pw != 1 || p.sh != p.sw ||
+            (p.sh != 1 && p.sh != 2) || vec != full || k.W % vec != 0 || k.cbs != k.W / vec || k.cbs < 1 || k.cbs > 64 ||
+            k.spw != 64 / k.cbs || k.Wo * p.sw != k.W || k.Ho != (k.H + 2 - 3) / p.sh + 1 || k.rc < 1 || k.chunks < 1 ||
+            (int64_t)(k.chunks - 1) * k.rc * p.sh >= k.H || (int64_t)k.div_cbs.d != k.cbs || (int64_t)k.div_chunks.d != k.chunks ||
+            (int64_t)k.div_c.d != k.C || (uint64_t)grid * 4 * k.spw < k.units)
+            return BS_ERR_UNSUPPORTED;
+#define BS_LAUNCH_MAXROWS(DT, V)                                                               \
+    do {                                                                                       \
+        if (p.sh == 2 && n_add == 0) bwd_maxrows_kernel<DT, V, 2, 0><<<g, b, 0, st>>>(k);      \
+        else if (p.sh == 2) bwd_maxrows_kernel<DT, V, 2, K_MAX_RES><<<g, b, 0, st>>>(k);       \
+        else if (n_add == 0) bwd_maxrows_kernel<DT, V, 1, 0><<<g, b, 0, st>>>(k);              \
+        else bwd_maxrows_kernel<DT, V, 1, K_MAX_RES><<<g, b, 0, st>>>(k);                      \
+    } while (0)
+        if (dtype == BS_F32) BS_LAUNCH_MAXROWS(DT_F32, 4);
+        else if (dtype == BS_BF16) BS_LAUNCH_MAXROWS(DT_BF16, 8);
+        else if (dtype == BS_F16) BS_LAUNCH_MAXROWS(DT_F16, 8);
+        else return BS_ERR_UNSUPPORTED;
+#undef BS_LAUNCH_MAXROWS
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            set_error(e);
+            return BS_ERR_HIP;
+        }
+        return BS_OK;
     }
     if (k.direct) {
         const PoolK &p = k.pool;

@@ -246,6 +246,7 @@ struct NhwcTile2K {
 // Backward pass of one stage: element-wise operations followed by at most one pooling
 // operation (pool.kind == 0: none).  Dense tensors only, row-major (NCHW) or channels-last.
 constexpr int K_BWD_EW = 16;
+constexpr int K_BWD_MAXROWS_RC = 8;  // window rows per chunk of the backward kernel that finds max-pooling picks itself
 struct BwdK {
     const void *a;        // the stage's input of the forward pass
     const void *g_out;    // gradient with respect to the stage's output
@@ -270,6 +271,14 @@ struct BwdK {
     int32_t flat;         // 1 (row-major, no pooling): planes are no whole number of vectors; the tensor is one run of
                           // `vec`-element vectors that may begin in one plane and end in the next; total = vectors,
                           // div_w divides by H * W
+    // own_picks = 1 (row-major, max pooling 3 x 3 with padding 1 and stride 1 or 2, rows of at most 64 vectors): a lane
+    // owns one column block and walks down a chunk of rows with the rows of the current windows in registers, finds
+    // every window's pick itself and exchanges the gradients of picks in its neighbours' columns inside the wave
+    // (idx unused).  A wave holds spw = 64 / cbs (plane, chunk) segments of cbs lanes; a chunk is rc window rows.
+    int32_t own_picks;
+    int32_t cbs, spw, chunks, rc;
+    uint32_t units;       // planes * chunks
+    FastDiv div_cbs, div_chunks;
 };
 
 #if defined(__HIPCC__)

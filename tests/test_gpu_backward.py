@@ -109,6 +109,44 @@ def test_small_stacks_vector_and_ragged_rows(name, dtype):
         check(layers, (2, 5, 13, 11), dtype, name + "/ragged rows", seed=3)  # one cell per lane
 
 
+def _own_pick_stacks(c):
+    return {
+        "stem": [wl.bn_params(c, 30), wl.relu(), wl.maxpool(3, 2, 1)],
+        "stem_add": [wl.bn_params(c, 31), wl.add(), wl.leaky_relu(0.1), wl.maxpool(3, 2, 1)],
+        "max3s1": [wl.bn_params(c, 32), wl.relu(), wl.maxpool(3, 1, 1)],
+        "pool_only": [wl.maxpool(3, 2, 1)],
+        "two_adds_s1": [wl.add(), wl.bn_params(c, 33), wl.add(), wl.clamp(-0.5, 1.0), wl.maxpool(3, 1, 1)],
+        "chain": [wl.maxpool(3, 1, 1), wl.bn_params(c, 34), wl.relu(), wl.maxpool(3, 2, 1), wl.bn_params(c, 35), wl.relu()],
+    }
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("shape", [(2, 3, 12, 16), (1, 2, 40, 32), (1, 2, 37, 24), (2, 2, 7, 8), (1, 1, 1, 8), (1, 2, 5, 256),
+                                   (1, 1, 9, 264), (2, 1, 70, 16)])
+def test_overlapping_max_windows_without_recorded_picks(shape, dtype):
+    """3 x 3 max windows (stride 1 and 2, padding 1) on rows of whole vectors: the lanes of a row find the picks
+    themselves.  Several chunks of rows, odd heights, one row, rows that fill a wave (64 column blocks) or do not
+    fit one (264 float32 columns: recorded picks again).  Against the oracle, and bit for bit against the
+    kernel that gathers recorded picks: both sum a cell's windows in the same order."""
+    for name, layers in _own_pick_stacks(shape[1]).items():
+        label = f"own picks/{name}"
+        x, res, dy = _inputs(layers, shape, 7, dtype)
+        x[:, :, ::2, 1::3] = 0.5   # ties inside windows
+        ref_x, ref_res = bw.backward_stack(layers, x, res, dy, dtype)
+        print(f"[backward] {label} shape={shape} dtype={dtype}", flush=True)
+        gx, gres, _ = run_gpu(layers, x, res, dy, dtype)
+        hx, hres, _ = run_gpu(layers, x, res, dy, dtype, lane_exchange=-1)
+        _close(gx, ref_x, dtype, label + " grad_x")
+        assert np.array_equal(gx.view(np.uint32), hx.view(np.uint32)), label
+        for i, (a, b, c) in enumerate(zip(gres, ref_res, hres)):
+            _close(a, b, dtype, f"{label} grad_residual[{i}]")
+            assert np.array_equal(a.view(np.uint32), c.view(np.uint32)), label
+    st = bs.Stack(_own_pick_stacks(shape[1])["stem"], shape, dtype).plan().plan_backward()
+    fits = shape[3] // (4 if dtype == "f32" else 8) <= 64
+    assert (bs.bs_stack_backward_workspace_bytes(st.handle) == 0) == fits
+    st.close()
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_disjoint_two_by_two_windows(dtype):
     c = 6
@@ -269,14 +307,23 @@ def test_single_stage_stacks_need_no_workspace_and_max_pooling_does():
     st = bs.Stack([wl.bn_params(8, 1), wl.relu(), wl.maxpool(2, 2)], (2, 8, 8, 8), "f32").plan().plan_backward()
     assert bs.bs_stack_backward_num_stages(st.handle) == 1 and bs.bs_stack_backward_workspace_bytes(st.handle) == 0
     st.close()
+    # overlapping 3 x 3 windows on rows of whole vectors: the same, the lanes of a row exchanging picks in their edge columns
     st = bs.Stack([wl.bn_params(8, 1), wl.relu(), wl.maxpool(3, 2, 1)], (2, 8, 8, 8), "f32").plan().plan_backward()
-    assert bs.bs_stack_backward_workspace_bytes(st.handle) >= 2 * 8 * 4 * 4 * 4  # the picks
+    assert bs.bs_stack_backward_num_stages(st.handle) == 1 and bs.bs_stack_backward_workspace_bytes(st.handle) == 0
     st.close()
+    # ... and with recorded picks where that kernel does not apply or is switched off
+    for layers, shape, opts in (([wl.bn_params(8, 1), wl.relu(), wl.maxpool(3, 2, 1)], (2, 8, 8, 8), dict(lane_exchange=-1)),
+                                ([wl.bn_params(8, 1), wl.relu(), wl.maxpool(3, 2, 1)], (2, 8, 8, 10), {}),
+                                ([wl.bn_params(8, 1), wl.relu(), wl.maxpool(5, 2, 2)], (2, 8, 8, 8), {})):
+        st = bs.Stack(layers, shape, "f32").plan(**opts).plan_backward()
+        out = wl.output_shape(layers, shape)
+        assert bs.bs_stack_backward_workspace_bytes(st.handle) >= int(np.prod(out)) * 4  # the picks
+        st.close()
 
 
 def test_argument_errors():
     layers = [wl.bn_params(8, 1), wl.relu(), wl.maxpool(3, 2, 1)]
-    st = bs.Stack(layers, (2, 8, 8, 8), "f32").plan()
+    st = bs.Stack(layers, (2, 8, 8, 8), "f32").plan(lane_exchange=-1)  # recorded picks: a workspace
     x = torch.zeros(2, 8, 8, 8, device="cuda")
     dy = torch.zeros(2, 8, 4, 4, device="cuda")
     gx = torch.empty_like(x)
@@ -299,7 +346,7 @@ def test_argument_errors():
         bs.bs_stack_backward(st.handle, 0, [], None, dy.data_ptr(), gx.data_ptr(), [], ws.data_ptr(), n, 0)
     assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_NULL"]
     # a new forward plan drops the backward plan
-    st.plan()
+    st.plan(lane_exchange=-1)
     assert bs.bs_stack_backward_num_stages(st.handle) == -1
     st.close()
 
