@@ -70,6 +70,17 @@ bs_status make_forward(const bs_stack *s, BwdStage &g, bool host_only)
     return BS_OK;
 }
 
+// Overlapping 3 x 3 windows (padding 1, stride 1 or 2 that divides the row exactly) on row-major planes whose
+// rows are whole vectors and fit one wave: the kernel whose lanes walk down the rows applies.
+bool walks_rows(const bs_stack *s, const BwdStage &g)
+{
+    const PoolK &p = g.k.pool;
+    const int32_t full = s->dtype == BS_F32 ? 4 : 8;
+    return s->opts.layout != BS_LAYOUT_NHWC && s->opts.lane_exchange >= 0 && (p.kind == OP_MAXPOOL || p.kind == OP_AVGSUM) &&
+           p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && g.k.W % full == 0 &&
+           g.k.W / full <= 64 && g.k.Wo * p.sw == g.k.W && g.k.Ho == (g.k.H + 2 - 3) / p.sh + 1;
+}
+
 }  // namespace
 
 namespace bs {
@@ -152,6 +163,20 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
         }
         if (open) close((int32_t)stack->layers.size() - 1);
         if (plan->stages.empty()) st = BS_ERR_UNSUPPORTED;
+        // a stage of element-wise operations only (no Add) behind a max pooling whose kernel finds the picks itself
+        // joins that stage: the kernel has the pooling's output at hand (the window maxima) and scales the
+        // windows' gradients by the operations' derivatives there -- no kernel, no recomputed input for them
+        for (size_t j = 0; j + 1 < plan->stages.size(); ++j) {
+            BwdStage &g = plan->stages[j];
+            const BwdStage &nx = plan->stages[j + 1];
+            bool plain = nx.k.pool.kind == 0 && nx.n_res == 0 && g.k.n_ew + nx.k.n_ew <= K_BWD_EW;
+            if (!plain || g.k.pool.kind != OP_MAXPOOL || !walks_rows(stack, g)) continue;
+            for (int32_t q = 0; q < nx.k.n_ew; ++q) g.k.ew[g.k.n_ew + q] = nx.k.ew[q];
+            g.k.n_post = nx.k.n_ew;
+            g.n_layers += nx.n_layers;
+            std::memcpy(g.out_shape, nx.out_shape, sizeof g.out_shape);
+            plan->stages.erase(plan->stages.begin() + (long)j + 1);
+        }
 
         // ---- launch geometry, forward stacks, workspace
         const uint64_t es = dtype_size(stack->dtype);
@@ -188,12 +213,10 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
                 }
                 lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 2 : 1);
                 g.k.div_wv = make_fastdiv((uint32_t)(g.k.flat ? 1 : g.k.W / g.vec));
-                // overlapping 3 x 3 max windows on rows that fit one wave: the kernel that finds the picks itself
-                if (p.kind == OP_MAXPOOL && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && p.sh == p.sw &&
-                    (p.sh == 1 || p.sh == 2) && g.vec == full && g.k.W / full <= 64 && g.k.Wo * p.sw == g.k.W &&
-                    g.k.Ho == (g.k.H + 2 - 3) / p.sh + 1 && stack->opts.lane_exchange >= 0) {
+                // overlapping 3 x 3 windows on rows that fit one wave: the kernel whose lanes walk down the rows
+                if (walks_rows(stack, g) && g.vec == full) {
                     BwdK &k = g.k;
-                    k.own_picks = 1;
+                    k.wave_rows = 1;
                     k.cbs = k.W / full;
                     k.spw = 64 / k.cbs;
                     // window rows per chunk: a chunk also visits the window rows just above and below it
@@ -215,8 +238,8 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
             g.k.div_c = make_fastdiv((uint32_t)g.k.C);
             g.threads = 256;
             g.grid = (int64_t)((lanes + 255) / 256);
-            if (g.k.own_picks) g.grid = ((int64_t)g.k.units + 4 * g.k.spw - 1) / (4 * g.k.spw);  // whole segments per wave
-            const bool is_max = p.kind == OP_MAXPOOL && !g.k.direct && !g.k.own_picks;  // recorded picks needed
+            if (g.k.wave_rows) g.grid = ((int64_t)g.k.units + 4 * g.k.spw - 1) / (4 * g.k.spw);  // whole segments per wave
+            const bool is_max = p.kind == OP_MAXPOOL && !g.k.direct && !g.k.wave_rows;  // recorded picks needed
             // the buffers are sized by these shapes: a stage must end where the next one begins
             const int64_t *next = j + 1 < S ? plan->stages[j + 1].in_shape : stack->out_shape;
             if (std::memcmp(g.out_shape, next, sizeof g.out_shape) != 0) { st = BS_ERR_SHAPE; break; }
@@ -322,7 +345,7 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         void *out = j + 1 < S ? ws + plan.stages[j + 1].a_off : ws + plan.last_out_off;
         const void *res[K_MAX_RES] = {nullptr, nullptr, nullptr, nullptr};
         for (int32_t r = 0; r < g.n_res; ++r) res[r] = residuals[g.res_map[r]];
-        const bool picks = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.own_picks;
+        const bool picks = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.wave_rows;
         int32_t *idx[1] = {picks ? reinterpret_cast<int32_t *>(ws + g.idx_off) : nullptr};
         const bs_status st = bs_stack_run(g.forward, a, res, out, g.forward->n_idx > 0 ? idx : nullptr,
                                           ws + plan.fwd_ws_off, plan.fwd_ws_bytes, stream);
@@ -335,7 +358,7 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         k.a = j == 0 ? in : ws + g.a_off;
         k.g_out = j + 1 == S ? grad_out : ws + plan.stages[j + 1].g_off;
         k.g_in = j == 0 ? grad_in : ws + g.g_off;
-        k.idx = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.own_picks ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
+        k.idx = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.wave_rows ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
         if (k.idx && j + 1 == S && kept(g)) k.idx = kept(g);
         k.params = stack->dev_params;
         bool wanted = k.g_in != nullptr;

@@ -46,9 +46,11 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // NR: residual gradients kept (K_MAX_RES, or 0 for a stage without Add: no registers for them).
 // FLAT (row-major only): nfirst[j] cells of row j lie in channel c[j], the rest in the next channel
 // (a vector that straddles two planes).  Otherwise every cell of row j lies in channel c[j].
+// The list is k.ew[first .. first + count).
 template <int DT, int VEC, int R, bool CL, int NR, bool FLAT>
 BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC],
-                             float (&t)[R][VEC], float (&r)[NR ? NR : 1][R][VEC], const uint32_t (&nfirst)[R])
+                             float (&t)[R][VEC], float (&r)[NR ? NR : 1][R][VEC], const uint32_t (&nfirst)[R], int32_t first,
+                             int32_t count)
 {
 #pragma unroll
     for (int j = 0; j < R; ++j)
@@ -60,7 +62,7 @@ BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_
         }
     int32_t adds = 0;
 #pragma clang loop unroll(disable)
-    for (int32_t q = 0; q < k.n_ew; ++q) {
+    for (int32_t q = first; q < first + count; ++q) {
         const int32_t kind = k.ew[q].kind, arg = k.ew[q].arg;
         if (kind == OP_ADD) {
             if constexpr (NR == 0) continue;  // instances for stages without Add (chosen at launch): nothing to read
@@ -181,7 +183,7 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
                         float (&r)[NR ? NR : 1][R][VEC])
 {
     const uint32_t none[R] = {};
-    return ew_sweep_impl<DT, VEC, R, CL, NR, false>(k, c, off, x, t, r, none);
+    return ew_sweep_impl<DT, VEC, R, CL, NR, false>(k, c, off, x, t, r, none, 0, k.n_ew);
 }
 
 // Write grad_in = s * t and grad_residual[n] = s * r[n] for one register row.
@@ -419,8 +421,8 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
         unpack<DT, VEC>(ar[u], x[u]);
         unpack<DT, VEC>(gr[u], s[u]);
     }
-    const int32_t adds = k.flat ? ew_sweep_impl<DT, VEC, U, false, NR, true>(k, cs, offs, x, t, r, nfirst)
-                                : ew_sweep_impl<DT, VEC, U, false, NR, false>(k, cs, offs, x, t, r, nfirst);
+    const int32_t adds = k.flat ? ew_sweep_impl<DT, VEC, U, false, NR, true>(k, cs, offs, x, t, r, nfirst, 0, k.n_ew)
+                                : ew_sweep_impl<DT, VEC, U, false, NR, false>(k, cs, offs, x, t, r, nfirst, 0, k.n_ew);
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (live[u]) store_row<DT, VEC, U, NR>(k, u, offs[u], adds, s[u], t, r);
@@ -497,30 +499,35 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 }
 
 // =============================================================================
-// bwd_maxrows_kernel: a stage whose max pooling has overlapping 3 x 3 windows (padding 1, stride
-// S = 1 or 2; BatchNorm -> ReLU -> MaxPool of the ResNet stem) on planes whose rows fit one wave.
-// No recorded picks and no recomputation pass: the stage input, the upstream gradient and the
-// gradient with respect to the input move once.
+// bwd_rows_kernel: a stage whose pooling has overlapping 3 x 3 windows (padding 1, stride S = 1 or
+// 2; BatchNorm -> ReLU -> MaxPool of the ResNet stem, the stacked pooling blocks of Section 4.4)
+// on planes whose rows fit one wave.  No recorded picks and no recomputation pass: the stage
+// input, the upstream gradient and the gradient with respect to the input move once.
 //
 // The lanes of a plane's row sit side by side in one wave (a lane owns one column block of VEC
 // cells, as in the forward sliding-window kernels) and walk down a chunk of rows.  A lane keeps
 // the three input rows of the current window row in registers: the values after the element-wise
 // list (with its neighbours' edge columns, one lane-shift each), the list's derivative factors,
 // and the gradient sums collected so far.  Per window row it reads S new input rows and its VO =
-// VEC / S upstream gradients, finds each of its windows' first maximum (row-major, as the forward
-// kernels do), adds the window's gradient to the picked cell -- a pick in a neighbour's column
-// travels there by one lane-shift -- and writes the S rows no later window touches.  A cell sums
-// its windows in row-major window order (earlier window rows first; within a row the left
-// neighbour's window, the lane's own windows from left to right, the right neighbour's window):
-// no atomics, the same bits on every run.
+// VEC / S upstream gradients and writes the S rows no later window touches.
+//   Max pooling: the lane finds each of its windows' first maximum (row-major, as the forward
+//   kernels do) and adds the window's gradient to the picked cell -- a pick in a neighbour's
+//   column travels there by one lane-shift.  Element-wise operations behind the pooling
+//   (k.n_post of them) are differentiated at the window maximum, which is the pooling's output.
+//   Average pooling: every window's gradient, times the reciprocal of the divisor the forward
+//   pass used, goes to all of the window's cells; the windows of the neighbouring lanes that
+//   reach into the block arrive by lane-shift.
+// A cell sums its windows in row-major window order (earlier window rows first; within a row the
+// left neighbour's window, the lane's own windows from left to right, the right neighbour's
+// window): no atomics, the same bits on every run.
 //
 // Chunks overlap: the rows a chunk writes are [rc * S * chunk, rc * S * (chunk + 1)) (to the end
 // of the plane for the last one); it also visits the window row above and the one below, whose
 // other rows belong to the neighbouring chunks.  Every lane of a wave runs the same number of
 // iterations whether or not its windows exist.
 // =============================================================================
-template <int DT, int VEC, int S, int NR>
-__global__ __launch_bounds__(256) void bwd_maxrows_kernel(const BwdK k)
+template <int DT, int VEC, int S, int NR, bool MAX>
+__global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
 {
     constexpr int K = 3, P = 1, VO = VEC / S, NL = P, NX = K - S - P, CW = NL + VEC + NX;
     constexpr int KEEP = K - S;  // rows two consecutive window rows share
@@ -581,43 +588,83 @@ __global__ __launch_bounds__(256) void bwd_maxrows_kernel(const BwdK k)
         unpack<DT, VO>(load_raw<DT, VO>(k.g_out, oplane + (uint32_t)(min(max(oh, 0), k.Ho - 1) * k.Wo + L.j * VO)), g);
 #pragma unroll
         for (int e = 0; e < VO; ++e) g[e] = row_ok ? g[e] : 0.0f;
-        // first maximum of every window: code = window row * K + window column
-        int32_t pick[VO];
+        if constexpr (MAX) {
+            // first maximum of every window: code = window row * K + window column
+            int32_t pick[VO];
+            float best[1][VO];
 #pragma unroll
-        for (int e = 0; e < VO; ++e) {
-            float best = -INFINITY;
-            pick[e] = -1;
+            for (int e = 0; e < VO; ++e) {
+                best[0][e] = -INFINITY;
+                pick[e] = -1;
 #pragma unroll
-            for (int dh = 0; dh < K; ++dh)
+                for (int dh = 0; dh < K; ++dh)
 #pragma unroll
-                for (int dw = 0; dw < K; ++dw) {
-                    const float v = y[dh][e * S + dw];
-                    const bool more = v > best;
-                    best = more ? v : best;
-                    pick[e] = more ? dh * K + dw : pick[e];
+                    for (int dw = 0; dw < K; ++dw) {
+                        const float v = y[dh][e * S + dw];
+                        const bool more = v > best[0][e];
+                        best[0][e] = more ? v : best[0][e];
+                        pick[e] = more ? dh * K + dw : pick[e];
+                    }
+            }
+            // element-wise operations behind the pooling: their derivative at the window's maximum (the pooling's
+            // output, as the forward pass rounded it) scales the window's gradient
+            if (k.n_post > 0) {
+                float tp[1][VO], none[1][1][VO];
+                const uint32_t no_off[1] = {0}, all[1] = {VO};
+                const int32_t cs[1] = {L.c};
+#pragma unroll
+                for (int e = 0; e < VO; ++e) best[0][e] = row_ok ? best[0][e] : 0.0f;  // windows that do not exist: any finite value
+                ew_sweep_impl<DT, VO, 1, false, 0, false>(k, cs, no_off, best, tp, none, all, k.n_ew, k.n_post);
+#pragma unroll
+                for (int e = 0; e < VO; ++e) g[e] *= tp[0][e];
+            }
+            // gradients into the picked cells, in the order a cell's windows have in the plane
+#pragma unroll
+            for (int dh = 0; dh < K; ++dh) {
+                // picks in the neighbours' columns: the first window's first column lies in the left lane's block,
+                // the last window's last column (stride 1) in the right lane's
+                const float to_left = pick[0] == dh * K ? g[0] : 0.0f;
+                const float from_right = from_right_lane(to_left);
+                if constexpr (NX > 0) {
+                    const float to_right = pick[VO - 1] == dh * K + K - 1 ? g[VO - 1] : 0.0f;
+                    const float from_left = from_left_lane(to_right);
+                    s[dh][0] += has_left ? from_left : 0.0f;
                 }
-        }
-        // gradients into the picked cells, in the order a cell's windows have in the plane
 #pragma unroll
-        for (int dh = 0; dh < K; ++dh) {
-            // picks in the neighbours' columns: the first window's first column lies in the left lane's block,
-            // the last window's last column (stride 1) in the right lane's
-            const float to_left = pick[0] == dh * K ? g[0] : 0.0f;
-            const float from_right = from_right_lane(to_left);
-            float from_left = 0.0f;
+                for (int e = 0; e < VO; ++e)
+#pragma unroll
+                    for (int dw = 0; dw < K; ++dw) {
+                        const int col = e * S + dw - NL;  // the window cell's column in the lane's block
+                        if (col >= 0 && col < VEC) s[dh][col] += pick[e] == dh * K + dw ? g[e] : 0.0f;
+                    }
+                s[dh][VEC - 1] += has_right ? from_right : 0.0f;
+            }
+        } else {
+            // every window hands its gradient times the reciprocal of its divisor to all its cells: the same
+            // per-column sums for the K rows of this window row, in the plane's window order
+#pragma unroll
+            for (int e = 0; e < VO; ++e)
+                g[e] *= bwd_avg_inv(k.pool, k.H, k.W, min(max(oh, 0), k.Ho - 1), L.j * VO + e);
+            float add[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) add[e] = 0.0f;
+            const float from_right = from_right_lane(g[0]);  // the right lane's first window holds this lane's last column
             if constexpr (NX > 0) {
-                const float to_right = pick[VO - 1] == dh * K + K - 1 ? g[VO - 1] : 0.0f;
-                from_left = from_left_lane(to_right);
-                s[dh][0] += has_left ? from_left : 0.0f;
+                const float from_left = from_left_lane(g[VO - 1]);  // stride 1: the left lane's last window holds the first
+                add[0] += has_left ? from_left : 0.0f;
             }
 #pragma unroll
             for (int e = 0; e < VO; ++e)
 #pragma unroll
                 for (int dw = 0; dw < K; ++dw) {
-                    const int col = e * S + dw - NL;  // the window cell's column in the lane's block
-                    if (col >= 0 && col < VEC) s[dh][col] += pick[e] == dh * K + dw ? g[e] : 0.0f;
+                    const int col = e * S + dw - NL;
+                    if (col >= 0 && col < VEC) add[col] += g[e];
                 }
-            s[dh][VEC - 1] += has_right ? from_right : 0.0f;
+            add[VEC - 1] += has_right ? from_right : 0.0f;
+#pragma unroll
+            for (int dh = 0; dh < K; ++dh)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) s[dh][e] += add[e];
         }
         // the S rows no later window row holds are complete
 #pragma unroll
@@ -879,11 +926,16 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
                (int64_t)grid * threads < (int64_t)k.total) {
         return BS_ERR_UNSUPPORTED;
     }
-    if (k.own_picks) {
+    if (k.wave_rows) {
         const PoolK &p = k.pool;
         // what the kernel assumes: 3 x 3 max windows, padding 1, stride 1 or 2 that divides the row exactly;
         // a row's column blocks in one wave; chunks that cover the plane
-        if (k.direct || p.kind != OP_MAXPOOL || p.kh != 3 || p.kw != 3 || p.ph != 1 || p.pw != 1 || p.sh != p.sw ||
+        for (int32_t j = k.n_ew; j < k.n_ew + k.n_post; ++j)
+            if (k.ew[j].kind == OP_ADD) return BS_ERR_UNSUPPORTED;
+        if (k.n_post < 0 || k.n_ew + k.n_post > K_BWD_EW) return BS_ERR_UNSUPPORTED;
+        const bool is_max = p.kind == OP_MAXPOOL;
+        if (!is_max && k.n_post != 0) return BS_ERR_UNSUPPORTED;
+        if (k.direct || (p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 3 || p.kw != 3 || p.ph != 1 || p.pw != 1 || p.sh != p.sw ||
             (p.sh != 1 && p.sh != 2) || vec != full || k.W % vec != 0 || k.cbs != k.W / vec || k.cbs < 1 || k.cbs > 64 ||
             k.spw != 64 / k.cbs || k.Wo * p.sw != k.W || k.Ho != (k.H + 2 - 3) / p.sh + 1 || k.rc < 1 || k.chunks < 1 ||
             (int64_t)(k.chunks - 1) * k.rc * p.sh >= k.H || (int64_t)k.div_cbs.d != k.cbs || (int64_t)k.div_chunks.d != k.chunks ||
@@ -891,10 +943,14 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
             return BS_ERR_UNSUPPORTED;
 #define BS_LAUNCH_MAXROWS(DT, V)                                                               \
     do {                                                                                       \
-        if (p.sh == 2 && n_add == 0) bwd_maxrows_kernel<DT, V, 2, 0><<<g, b, 0, st>>>(k);      \
-        else if (p.sh == 2) bwd_maxrows_kernel<DT, V, 2, K_MAX_RES><<<g, b, 0, st>>>(k);       \
-        else if (n_add == 0) bwd_maxrows_kernel<DT, V, 1, 0><<<g, b, 0, st>>>(k);              \
-        else bwd_maxrows_kernel<DT, V, 1, K_MAX_RES><<<g, b, 0, st>>>(k);                      \
+        if (is_max && p.sh == 2 && n_add == 0) bwd_rows_kernel<DT, V, 2, 0, true><<<g, b, 0, st>>>(k);          \
+        else if (is_max && p.sh == 2) bwd_rows_kernel<DT, V, 2, K_MAX_RES, true><<<g, b, 0, st>>>(k);           \
+        else if (is_max && n_add == 0) bwd_rows_kernel<DT, V, 1, 0, true><<<g, b, 0, st>>>(k);                  \
+        else if (is_max) bwd_rows_kernel<DT, V, 1, K_MAX_RES, true><<<g, b, 0, st>>>(k);                        \
+        else if (p.sh == 2 && n_add == 0) bwd_rows_kernel<DT, V, 2, 0, false><<<g, b, 0, st>>>(k);              \
+        else if (p.sh == 2) bwd_rows_kernel<DT, V, 2, K_MAX_RES, false><<<g, b, 0, st>>>(k);                    \
+        else if (n_add == 0) bwd_rows_kernel<DT, V, 1, 0, false><<<g, b, 0, st>>>(k);                           \
+        else bwd_rows_kernel<DT, V, 1, K_MAX_RES, false><<<g, b, 0, st>>>(k);                                   \
     } while (0)
         if (dtype == BS_F32) BS_LAUNCH_MAXROWS(DT_F32, 4);
         else if (dtype == BS_BF16) BS_LAUNCH_MAXROWS(DT_BF16, 8);

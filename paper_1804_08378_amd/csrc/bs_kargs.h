@@ -271,11 +271,13 @@ struct BwdK {
     int32_t flat;         // 1 (row-major, no pooling): planes are no whole number of vectors; the tensor is one run of
                           // `vec`-element vectors that may begin in one plane and end in the next; total = vectors,
                           // div_w divides by H * W
-    // own_picks = 1 (row-major, max pooling 3 x 3 with padding 1 and stride 1 or 2, rows of at most 64 vectors): a lane
-    // owns one column block and walks down a chunk of rows with the rows of the current windows in registers, finds
-    // every window's pick itself and exchanges the gradients of picks in its neighbours' columns inside the wave
-    // (idx unused).  A wave holds spw = 64 / cbs (plane, chunk) segments of cbs lanes; a chunk is rc window rows.
-    int32_t own_picks;
+    // wave_rows = 1 (row-major, pooling 3 x 3 with padding 1 and stride 1 or 2, rows of at most 64 vectors): a lane
+    // owns one column block and walks down a chunk of rows with the rows of the current windows in registers; max
+    // pooling: it finds every window's pick itself (idx unused); gradients that belong to its neighbours' columns
+    // travel inside the wave.  A wave holds spw = 64 / cbs (plane, chunk) segments of cbs lanes; a chunk is rc window rows.
+    int32_t wave_rows;
+    int32_t n_post;       // wave_rows, max pooling: element-wise operations (no Add) that follow the pooling, ew[n_ew .. n_ew + n_post):
+                          // g_out is the gradient with respect to their output
     int32_t cbs, spw, chunks, rc;
     uint32_t units;       // planes * chunks
     FastDiv div_cbs, div_chunks;

@@ -117,6 +117,9 @@ def _own_pick_stacks(c):
         "pool_only": [wl.maxpool(3, 2, 1)],
         "two_adds_s1": [wl.add(), wl.bn_params(c, 33), wl.add(), wl.clamp(-0.5, 1.0), wl.maxpool(3, 1, 1)],
         "chain": [wl.maxpool(3, 1, 1), wl.bn_params(c, 34), wl.relu(), wl.maxpool(3, 2, 1), wl.bn_params(c, 35), wl.relu()],
+        "avg3s1": [wl.bn_params(c, 37), wl.relu(), wl.avgpool(3, 1, 1, True)],
+        "avg3s2_in_range_count": [wl.add(), wl.bn_params(c, 38), wl.avgpool(3, 2, 1, False)],
+        "halo_stress": [wl.bn_params(c, 39), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1), wl.bn_params(c, 40), wl.relu()],
     }
 
 
@@ -137,14 +140,25 @@ def test_overlapping_max_windows_without_recorded_picks(shape, dtype):
         gx, gres, _ = run_gpu(layers, x, res, dy, dtype)
         hx, hres, _ = run_gpu(layers, x, res, dy, dtype, lane_exchange=-1)
         _close(gx, ref_x, dtype, label + " grad_x")
-        assert np.array_equal(gx.view(np.uint32), hx.view(np.uint32)), label
+        _close(hx, ref_x, dtype, label + " grad_x (recorded picks)")
+        # the operations behind the last pooling join its stage (no gradient rounded to 16 bits in between)
+        # (and the average's box sums add in another order than the gather does: no common bits there)
+        same_bits = (dtype == "f32" or name not in ("chain", "halo_stress")) and "avg" not in name and name != "halo_stress"
+        assert not same_bits or np.array_equal(gx.view(np.uint32), hx.view(np.uint32)), label
         for i, (a, b, c) in enumerate(zip(gres, ref_res, hres)):
             _close(a, b, dtype, f"{label} grad_residual[{i}]")
-            assert np.array_equal(a.view(np.uint32), c.view(np.uint32)), label
+            assert not same_bits or np.array_equal(a.view(np.uint32), c.view(np.uint32)), label
     st = bs.Stack(_own_pick_stacks(shape[1])["stem"], shape, dtype).plan().plan_backward()
     fits = shape[3] // (4 if dtype == "f32" else 8) <= 64
     assert (bs.bs_stack_backward_workspace_bytes(st.handle) == 0) == fits
     st.close()
+    # max pool, BatchNorm, ReLU: one stage where the lanes find the picks, two otherwise
+    layers = [wl.maxpool(3, 2, 1), wl.bn_params(shape[1], 36), wl.relu()]
+    for opts, want in (({}, 1 if fits else 2), (dict(lane_exchange=-1), 2)):
+        st = bs.Stack(layers, shape, dtype).plan(**opts).plan_backward()
+        assert bs.bs_stack_backward_num_stages(st.handle) == want
+        st.close()
+    check(layers, shape, dtype, "own picks/pool_bn_relu", seed=9)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
@@ -380,13 +394,13 @@ def test_saved_indices_replace_the_recomputation(dtype, layout):
 
 def test_forward_and_backward_can_be_captured_in_a_hip_graph_and_replayed():
     """bs_stack_backward only enqueues kernels (its recomputation passes included): a training step's
-    forward and backward pass of a three-stage stack are captured once and replayed with new operands,
+    forward and backward pass of a two-stage stack are captured once and replayed with new operands,
     eager calls in between; every replay matches the oracle."""
     c = 6
     layers = [wl.bn_params(c, 5), wl.add(), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1), wl.bn_params(c, 6), wl.relu()]
     shape, oshape = (2, c, 24, 32), (2, c, 12, 16)
     st = bs.Stack(layers, shape, "f32").plan().plan_backward()
-    assert bs.bs_stack_backward_num_stages(st.handle) == 3
+    assert bs.bs_stack_backward_num_stages(st.handle) == 2  # BatchNorm, ReLU behind the max pooling join its stage
     x_s, r_s, dy_s = (torch.zeros(sh, device="cuda") for sh in (shape, shape, oshape))
     out, _ = st.alloc_outputs("cuda", False)
     gx, gr = torch.empty_like(x_s), torch.empty_like(r_s)
