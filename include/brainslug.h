@@ -438,6 +438,26 @@ BS_API bs_status bs_stack_backward(const bs_stack *stack, const void *in, const 
                                    void *stream);
 
 /*
+ * bs_stack_backward for operands that are channel slices of larger tensors (Section 5, DenseNet-121:
+ * the dense layers' BatchNorm -> ReLU read a prefix of the block's concatenation buffer, and the
+ * gradients of the buffer's channel ranges are slices of one gradient buffer): `in`, `grad_out`
+ * and `grad_in` are read and written in place, with batch strides as in bs_stack_run_strided
+ * (0 = dense; row-major: elements between consecutive images; channels-last: H * W times the
+ * larger tensor's channel count).  Residual operands, their gradients, saved indices and the
+ * workspace are dense.  No output may overlap an input, the workspace or another output; two
+ * slices of one buffer with the same batch stride count as disjoint when their per-image byte
+ * ranges are.  A stage without pooling on planes that are no whole number of 128-bit vectors
+ * takes slices only when C * H * W is one (BS_ERR_UNSUPPORTED otherwise).
+ * Errors: those of bs_stack_backward; BS_ERR_SHAPE / BS_ERR_ALIGN for the strides as in
+ *         bs_stack_run_strided.
+ */
+BS_API bs_status bs_stack_backward_strided(const bs_stack *stack, const void *in, int64_t in_batch_stride,
+                                           const void *const *residuals, const int32_t *const *indices,
+                                           const void *grad_out, int64_t grad_out_batch_stride, void *grad_in,
+                                           int64_t grad_in_batch_stride, void *const *grad_residuals, void *workspace,
+                                           uint64_t workspace_bytes, void *stream);
+
+/*
  * Compile, without loading them and without touching any device, all run-time builds the
  * current plan (device or host-only) asks for, for GPU architecture `arch` ("gfx950"; NULL =
  * "gfx950").  A way to check on a machine without a GPU that a stack's kernels build.

@@ -110,6 +110,9 @@ _SIGNATURES = {
     "bs_stack_backward_num_stages": (C.c_int32, [C.c_void_p]),
     "bs_stack_backward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p,
                                     C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_stack_backward_strided": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                            C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.c_void_p,
+                                            C.c_uint64, C.c_void_p]),
     "bs_probe_issue_rate": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_uint64, C.c_void_p]),
     "bs_stack_jit_check": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]),
     "bs_jit_log": (C.c_char_p, []),
@@ -391,6 +394,23 @@ def bs_stack_backward(handle, in_ptr, residual_ptrs, index_ptrs, grad_out_ptr, g
            "bs_stack_backward")
 
 
+def bs_stack_backward_strided(handle, in_ptr, in_batch_stride, residual_ptrs, index_ptrs, grad_out_ptr, grad_out_batch_stride,
+                              grad_in_ptr, grad_in_batch_stride, grad_residual_ptrs, workspace_ptr, workspace_bytes, stream) -> None:
+    """bs_stack_backward on channel slices: batch strides in elements (0 = dense)."""
+    res = gres = idx = None
+    if residual_ptrs:
+        res = (C.c_void_p * len(residual_ptrs))(*[C.c_void_p(p or None) for p in residual_ptrs])
+    if index_ptrs:
+        idx = (C.c_void_p * len(index_ptrs))(*[C.c_void_p(p or None) for p in index_ptrs])
+    if grad_residual_ptrs:
+        gres = (C.c_void_p * len(grad_residual_ptrs))(*[C.c_void_p(p or None) for p in grad_residual_ptrs])
+    _check(load().bs_stack_backward_strided(C.c_void_p(handle), C.c_void_p(in_ptr or None), int(in_batch_stride), res, idx,
+                                            C.c_void_p(grad_out_ptr or None), int(grad_out_batch_stride),
+                                            C.c_void_p(grad_in_ptr or None), int(grad_in_batch_stride), gres,
+                                            C.c_void_p(workspace_ptr or None), int(workspace_bytes), C.c_void_p(stream or None)),
+           "bs_stack_backward_strided")
+
+
 def bs_stack_run_strided(handle, in_ptr, in_batch_stride, residual_ptrs, out_ptr, out_batch_stride,
                          index_ptrs, workspace_ptr, workspace_bytes, stream) -> None:
     """bs_stack_run on channel slices: batch strides in elements (0 = dense)."""
@@ -633,11 +653,13 @@ class Stack:
             _check(rc, "bs_stack_run_strided")
         return out
 
-    def backward_unchecked(self, x, residuals, grad_out, grad_x, grad_residuals, indices=None):
-        """`bs_stack_backward` with as little Python in the way as possible: dense tensors of the plan's
+    def backward_unchecked(self, x, residuals, grad_out, grad_x, grad_residuals, indices=None, in_batch_stride=0,
+                           grad_out_batch_stride=0, grad_in_batch_stride=0):
+        """`bs_stack_backward_strided` with as little Python in the way as possible: tensors of the plan's
         layout and the stack's dtype that the caller has validated and allocated (`grad_x` and entries
         of `grad_residuals` may be None: not wanted; `indices`: the forward pass's index outputs or
-        None).  The library still checks alignment, aliasing and the workspace."""
+        None; batch strides in elements for `x`, `grad_out`, `grad_x` that are channel slices, 0 = dense).
+        The library still checks strides, alignment, aliasing and the workspace."""
         import torch
         if not self._bwd_planned:
             self.plan_backward()
@@ -648,11 +670,12 @@ class Stack:
         idx = (C.c_void_p * len(indices))(*[t.data_ptr() if t is not None else None for t in indices]) if indices else None
         raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
         st = raw_stream(x.device.index) if raw_stream is not None else torch.cuda.current_stream(x.device).cuda_stream
-        rc = load().bs_stack_backward(self.handle, x.data_ptr(), res, idx, grad_out.data_ptr(),
-                                      grad_x.data_ptr() if grad_x is not None else None, gres,
-                                      self.workspace(x.device, st, backward=True).data_ptr() if n else None, n, st)
+        rc = load().bs_stack_backward_strided(self.handle, x.data_ptr(), in_batch_stride, res, idx, grad_out.data_ptr(),
+                                              grad_out_batch_stride, grad_x.data_ptr() if grad_x is not None else None,
+                                              grad_in_batch_stride, gres,
+                                              self.workspace(x.device, st, backward=True).data_ptr() if n else None, n, st)
         if rc != 0:
-            _check(rc, "bs_stack_backward")
+            _check(rc, "bs_stack_backward_strided")
 
     def _run_nhwc(self, x, residuals, out, indices, stream):
         """A channels-last plan: every tensor is in torch's channels_last memory format."""

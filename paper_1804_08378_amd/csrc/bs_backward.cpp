@@ -20,6 +20,10 @@
 #include <cstring>
 #include <new>
 
+#if defined(BS_BWD_AUDIT)
+#include <hip/hip_runtime.h>
+#endif
+
 #include "bs_internal.h"
 
 using namespace bs;
@@ -71,13 +75,15 @@ bs_status make_forward(const bs_stack *s, BwdStage &g, bool host_only)
 }
 
 // Overlapping 3 x 3 windows (padding 1, stride 1 or 2 that divides the row exactly) on row-major planes whose
-// rows are whole vectors and fit one wave: the kernel whose lanes walk down the rows applies.
+// rows are whole vectors and fit one wave: the kernel whose lanes walk down the rows applies.  Average pooling
+// with stride 1 stays with the gather kernel (measured on MI355X, 56 x 56 planes: 151 us against 165 us -- one
+// new row per iteration does not pay for the iteration; for max pooling the saved recomputation pass does).
 bool walks_rows(const bs_stack *s, const BwdStage &g)
 {
     const PoolK &p = g.k.pool;
     const int32_t full = s->dtype == BS_F32 ? 4 : 8;
-    return s->opts.layout != BS_LAYOUT_NHWC && s->opts.lane_exchange >= 0 && (p.kind == OP_MAXPOOL || p.kind == OP_AVGSUM) &&
-           p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && g.k.W % full == 0 &&
+    return s->opts.layout != BS_LAYOUT_NHWC && s->opts.lane_exchange >= 0 &&
+           (p.kind == OP_MAXPOOL || (p.kind == OP_AVGSUM && p.sh == 2)) && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && g.k.W % full == 0 &&
            g.k.W / full <= 64 && g.k.Wo * p.sw == g.k.W && g.k.Ho == (g.k.H + 2 - 3) / p.sh + 1;
 }
 
@@ -273,6 +279,21 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
     return st;
 }
 
+#if defined(BS_BWD_AUDIT)
+// Audit builds: 64 device counters, one per checked access site of the backward kernels.
+static uint32_t *audit_counters()
+{
+    static uint32_t *p = nullptr;
+    if (!p && hipMalloc(reinterpret_cast<void **>(&p), 64 * sizeof(uint32_t)) == hipSuccess) (void)hipMemset(p, 0, 64 * sizeof(uint32_t));
+    return p;
+}
+extern "C" __attribute__((visibility("default"))) int32_t bs_backward_audit_read(uint32_t *out64)
+{
+    uint32_t *p = audit_counters();
+    return p && hipMemcpy(out64, p, 64 * sizeof(uint32_t), hipMemcpyDeviceToHost) == hipSuccess ? 0 : 1;
+}
+#endif
+
 extern "C" uint64_t bs_stack_backward_workspace_bytes(const bs_stack *stack)
 {
     return stack && stack->backward ? stack->backward->workspace_bytes : 0;
@@ -288,6 +309,16 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
                                        void *const *grad_residuals, void *workspace, uint64_t workspace_bytes,
                                        void *stream)
 {
+    return bs_stack_backward_strided(stack, in, 0, residuals, indices, grad_out, 0, grad_in, 0, grad_residuals, workspace,
+                                     workspace_bytes, stream);
+}
+
+extern "C" bs_status bs_stack_backward_strided(const bs_stack *stack, const void *in, int64_t in_batch_stride,
+                                               const void *const *residuals, const int32_t *const *indices,
+                                               const void *grad_out, int64_t grad_out_batch_stride, void *grad_in,
+                                               int64_t grad_in_batch_stride, void *const *grad_residuals, void *workspace,
+                                               uint64_t workspace_bytes, void *stream)
+{
     if (!stack || !in || !grad_out) return BS_ERR_NULL;
     if (!stack->planned || !stack->device_planned || !stack->backward) return BS_ERR_NOT_PLANNED;
     if (current_device() != stack->device) return BS_ERR_DEVICE;
@@ -296,38 +327,45 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
     for (int32_t i = 0; i < stack->n_res; ++i)
         if (!residuals[i]) return BS_ERR_NULL;
 
-    // ---- the caller's buffers: alignment, workspace, no output over an input or another output
+    // ---- the caller's buffers: strides, alignment, workspace, no output over an input or another output
     const uint64_t es = dtype_size(stack->dtype);
-    struct Buf { const void *p; uint64_t bytes; };
-    Buf ins[2 + BS_MAX_RESIDUALS + 1], outs[1 + BS_MAX_RESIDUALS];
+    TensorBytes ins[2 + BS_MAX_RESIDUALS + 1 + BS_MAX_INDEX_OUTPUTS], outs[1 + BS_MAX_RESIDUALS];
     int n_in = 0, n_out = 0;
-    ins[n_in++] = Buf{in, numel(stack->in_shape) * es};
-    ins[n_in++] = Buf{grad_out, numel(stack->out_shape) * es};
-    for (int32_t i = 0; i < stack->n_res; ++i) ins[n_in++] = Buf{residuals[i], numel(stack->res_shape[i]) * es};
-    if (grad_in) outs[n_out++] = Buf{grad_in, numel(stack->in_shape) * es};
+    bs_status bst = resolve_slice(stack, stack->in_shape, in, in_batch_stride, ins[n_in++]);
+    if (bst != BS_OK) return bst;
+    bst = resolve_slice(stack, stack->out_shape, grad_out, grad_out_batch_stride, ins[n_in++]);
+    if (bst != BS_OK) return bst;
+    auto dense = [](const void *p, uint64_t bytes) { return TensorBytes{p, 1, bytes, bytes}; };
+    for (int32_t i = 0; i < stack->n_res; ++i) ins[n_in++] = dense(residuals[i], numel(stack->res_shape[i]) * es);
+    if (grad_in) {
+        bst = resolve_slice(stack, stack->in_shape, grad_in, grad_in_batch_stride, outs[n_out++]);
+        if (bst != BS_OK) return bst;
+    }
     for (int32_t i = 0; i < stack->n_res; ++i)
-        if (grad_residuals && grad_residuals[i]) outs[n_out++] = Buf{grad_residuals[i], numel(stack->res_shape[i]) * es};
+        if (grad_residuals && grad_residuals[i]) outs[n_out++] = dense(grad_residuals[i], numel(stack->res_shape[i]) * es);
     if (plan.workspace_bytes > 0) {
         if (!workspace || workspace_bytes < plan.workspace_bytes) return BS_ERR_WORKSPACE;
-        ins[n_in++] = Buf{workspace, plan.workspace_bytes};
+        ins[n_in++] = dense(workspace, plan.workspace_bytes);
     }
-    Buf saved[BS_MAX_INDEX_OUTPUTS];
-    int n_saved = 0;
     for (int32_t i = 0; i < stack->n_idx; ++i)
-        if (indices && indices[i]) saved[n_saved++] = Buf{indices[i], numel(stack->idx_shape[i]) * 4};
-    for (int i = 0; i < n_saved; ++i)
-        if (!aligned16(saved[i].p)) return BS_ERR_ALIGN;
+        if (indices && indices[i]) ins[n_in++] = dense(indices[i], numel(stack->idx_shape[i]) * 4);
     for (int i = 0; i < n_in; ++i)
         if (!aligned16(ins[i].p)) return BS_ERR_ALIGN;
     for (int i = 0; i < n_out; ++i) {
         if (!aligned16(outs[i].p)) return BS_ERR_ALIGN;
         for (int j = 0; j < n_in; ++j)
-            if (overlap(outs[i].p, outs[i].bytes, ins[j].p, ins[j].bytes)) return BS_ERR_ALIAS;
-        for (int j = 0; j < n_saved; ++j)
-            if (overlap(outs[i].p, outs[i].bytes, saved[j].p, saved[j].bytes)) return BS_ERR_ALIAS;
+            if (tensors_overlap(outs[i], ins[j])) return BS_ERR_ALIAS;
         for (int j = 0; j < i; ++j)
-            if (overlap(outs[i].p, outs[i].bytes, outs[j].p, outs[j].bytes)) return BS_ERR_ALIAS;
+            if (tensors_overlap(outs[i], outs[j])) return BS_ERR_ALIAS;
     }
+    // what the kernels add per image (row-major) or per pixel (channels-last) to reach a slice's elements
+    const bool nhwc = stack->opts.layout == BS_LAYOUT_NHWC;
+    auto extra = [&](const int64_t *shape, int64_t stride) -> uint32_t {
+        const int64_t image = shape[1] * shape[2] * shape[3];
+        return (uint32_t)(nhwc ? (stride - image) / (shape[2] * shape[3]) : stride - image);
+    };
+    const uint32_t a_extra = extra(stack->in_shape, in_batch_stride), gin_extra = grad_in ? extra(stack->in_shape, grad_in_batch_stride) : 0,
+                   gout_extra = extra(stack->out_shape, grad_out_batch_stride);
 
     char *ws = static_cast<char *>(workspace);
     const size_t S = plan.stages.size();
@@ -347,8 +385,8 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         for (int32_t r = 0; r < g.n_res; ++r) res[r] = residuals[g.res_map[r]];
         const bool picks = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.wave_rows;
         int32_t *idx[1] = {picks ? reinterpret_cast<int32_t *>(ws + g.idx_off) : nullptr};
-        const bs_status st = bs_stack_run(g.forward, a, res, out, g.forward->n_idx > 0 ? idx : nullptr,
-                                          ws + plan.fwd_ws_off, plan.fwd_ws_bytes, stream);
+        const bs_status st = bs_stack_run_strided(g.forward, a, j == 0 ? in_batch_stride : 0, res, out, 0,
+                                                  g.forward->n_idx > 0 ? idx : nullptr, ws + plan.fwd_ws_off, plan.fwd_ws_bytes, stream);
         if (st != BS_OK) return st;
     }
     // ---- gradients, last stage first
@@ -361,6 +399,18 @@ extern "C" bs_status bs_stack_backward(const bs_stack *stack, const void *in, co
         k.idx = g.k.pool.kind == OP_MAXPOOL && !g.k.direct && !g.k.wave_rows ? reinterpret_cast<const int32_t *>(ws + g.idx_off) : nullptr;
         if (k.idx && j + 1 == S && kept(g)) k.idx = kept(g);
         k.params = stack->dev_params;
+        k.a_extra = j == 0 ? a_extra : 0;
+        k.gin_extra = j == 0 ? gin_extra : 0;
+        k.gout_extra = j + 1 == S ? gout_extra : 0;
+#if defined(BS_BWD_AUDIT)
+        {
+            auto reach = [&](const TensorBytes &t) { return (uint32_t)(((t.images - 1) * t.stride_bytes + t.image_bytes) / es); };
+            k.audit_lim[0] = j == 0 ? reach(ins[0]) : (uint32_t)numel(g.in_shape);
+            k.audit_lim[1] = j + 1 == S ? reach(ins[1]) : (uint32_t)numel(g.out_shape);
+            k.audit_lim[2] = j == 0 && grad_in ? reach(outs[0]) : (uint32_t)numel(g.in_shape);
+            k.audit = audit_counters();
+        }
+#endif
         bool wanted = k.g_in != nullptr;
         for (int32_t r = 0; r < g.n_res; ++r) {
             k.res[r] = residuals[g.res_map[r]];

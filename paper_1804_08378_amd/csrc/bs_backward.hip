@@ -23,6 +23,24 @@
 
 namespace bs {
 
+
+// Build with -DBS_BWD_AUDIT to check every element offset into the stage input, the upstream gradient and the
+// input gradient against the extents the host passes (k.audit_lim[0..2], in elements) before it is used: an
+// offset outside is counted in k.audit[site] and replaced by 0, so such a build cannot read or write outside
+// those tensors.  Without the macro the checks compile to nothing.
+#if defined(BS_BWD_AUDIT)
+BS_DEV uint32_t audited(const BwdK &k, int which, int site, uint32_t off, uint32_t n)
+{
+    if (k.audit && (uint64_t)off + n > k.audit_lim[which]) {
+        atomicAdd(&k.audit[site], 1u);
+        return 0u;
+    }
+    return off;
+}
+#else
+BS_DEV uint32_t audited(const BwdK &, int, int, uint32_t off, uint32_t) { return off; }
+#endif
+
 // float32 reciprocal of the divisor of the average pooling window (oh, ow): the forward
 // kernels' rule (0: in-range cells, 1: kh * kw, 2: cells inside the padded plane).
 BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32_t ow)
@@ -187,15 +205,16 @@ BS_DEV int32_t ew_sweep(const BwdK &k, const int32_t (&c)[R], const uint32_t (&o
 }
 
 // Write grad_in = s * t and grad_residual[n] = s * r[n] for one register row.
+// gin_shift: what the element's offset in g_in exceeds `off` by (channel slices).
 template <int DT, int VEC, int R, int NR = K_MAX_RES>
-BS_DEV void store_row(const BwdK &k, int j, uint32_t off, int32_t adds, const float (&s)[VEC], const float (&t)[R][VEC],
-                      const float (&r)[NR ? NR : 1][R][VEC])
+BS_DEV void store_row(const BwdK &k, int j, uint32_t off, uint32_t gin_shift, int32_t adds, const float (&s)[VEC],
+                      const float (&t)[R][VEC], const float (&r)[NR ? NR : 1][R][VEC])
 {
     if (k.g_in) {
         float v[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) v[e] = s[e] * t[j][e];
-        store_elems<DT, VEC>(k.g_in, off, v);
+        store_elems<DT, VEC>(k.g_in, audited(k, 2, 23, off + gin_shift, VEC), v);
     }
 #pragma unroll
     for (int n = 0; n < NR; ++n)
@@ -245,7 +264,7 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
 
     // ---- 1. forward through the element-wise list, collecting derivative products
     float x[1][VEC], t[1][VEC], r[NR ? NR : 1][1][VEC];
-    unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x[0]);
+    unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, audited(k, 0, 1, off + img * k.a_extra, VEC)), x[0]);
     const uint32_t offs[1] = {off};
     const int32_t cs[1] = {c};
     const int32_t adds = ew_sweep<DT, VEC, 1, false, NR>(k, cs, offs, x, t, r);
@@ -253,8 +272,9 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
     // ---- 2. gradient with respect to the list's output
     float s[VEC];
     const PoolK &p = k.pool;
+    const uint32_t gsh = img * k.gout_extra;  // the upstream gradient's image starts this much later than a dense one's
     if (p.kind == 0) {
-        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.g_out, off), s);
+        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.g_out, audited(k, 1, 8, off + gsh, VEC)), s);
     } else {
         const bool is_max = p.kind == OP_MAXPOOL;
         const int32_t kh = KH ? KH : p.kh, kw = KH ? KW : p.kw, sh = KH ? SH : p.sh, sw = KH ? SW : p.sw;
@@ -289,9 +309,9 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
                 if constexpr (SW == 1 && NOW == VEC + 2) {
                     // stride 1 (the output row is as long as the input row: checked at launch): windows
                     // iw0 - 1 .. iw0 + VEC; the middle VEC of them are one aligned vector
-                    const Raw<DT, VEC> mid = load_raw<DT, VEC>(k.g_out, orow + (uint32_t)iw0);
-                    const Raw<DT, 1> left = load_raw<DT, 1>(k.g_out, orow + (uint32_t)max(iw0 - 1, 0));
-                    const Raw<DT, 1> right = load_raw<DT, 1>(k.g_out, orow + (uint32_t)min(iw0 + VEC, k.Wo - 1));
+                    const Raw<DT, VEC> mid = load_raw<DT, VEC>(k.g_out, audited(k, 1, 9, gsh + orow + (uint32_t)iw0, VEC));
+                    const Raw<DT, 1> left = load_raw<DT, 1>(k.g_out, audited(k, 1, 10, gsh + orow + (uint32_t)max(iw0 - 1, 0), 1));
+                    const Raw<DT, 1> right = load_raw<DT, 1>(k.g_out, audited(k, 1, 11, gsh + orow + (uint32_t)min(iw0 + VEC, k.Wo - 1), 1));
                     if (is_max) {
                         int32_t pm[VEC];
                         load_picks<VEC>(k.idx, orow + (uint32_t)iw0, pm);
@@ -312,8 +332,8 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
                     // stride 2 (the output row is half the input row: checked at launch): windows
                     // iw0 / 2 .. iw0 / 2 + VEC / 2; all but the last are one aligned vector
                     constexpr int HV = VEC / 2;
-                    const Raw<DT, HV> mid = load_raw<DT, HV>(k.g_out, orow + (uint32_t)ow0);
-                    const Raw<DT, 1> right = load_raw<DT, 1>(k.g_out, orow + (uint32_t)min(ow0 + HV, k.Wo - 1));
+                    const Raw<DT, HV> mid = load_raw<DT, HV>(k.g_out, audited(k, 1, 12, gsh + orow + (uint32_t)ow0, HV));
+                    const Raw<DT, 1> right = load_raw<DT, 1>(k.g_out, audited(k, 1, 13, gsh + orow + (uint32_t)min(ow0 + HV, k.Wo - 1), 1));
                     if (is_max) {
                         int32_t pm[HV];
                         load_picks<HV>(k.idx, orow + (uint32_t)ow0, pm);
@@ -332,7 +352,7 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
                     for (int b = 0; b < NOW; ++b) {
                         const uint32_t o = orow + (uint32_t)min(max(ow0 + b, 0), k.Wo - 1);
                         float g1[1];
-                        unpack<DT, 1>(load_raw<DT, 1>(k.g_out, o), g1);
+                        unpack<DT, 1>(load_raw<DT, 1>(k.g_out, audited(k, 1, 14, gsh + o, 1)), g1);
                         gv[b] = g1[0];
                         pick[b] = is_max ? k.idx[o] : 0;
                     }
@@ -361,7 +381,7 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
             for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
                 const uint32_t o = obase + (uint32_t)(oh * k.Wo + ow);  // 0 <= oh < Ho, 0 <= ow < Wo
                 float g[1];
-                unpack<DT, 1>(load_raw<DT, 1>(k.g_out, o), g);
+                unpack<DT, 1>(load_raw<DT, 1>(k.g_out, audited(k, 1, 15, gsh + o, 1)), g);
                 if (is_max) {
                     const int32_t d = k.idx[o] - cell0;  // the pick is one of the lane's cells if 0 <= d < VEC
 #pragma unroll
@@ -376,7 +396,7 @@ __global__ __launch_bounds__(256) void bwd_stage_kernel(const BwdK k)
     }
 
     // ---- 3. results
-    if (live) store_row<DT, VEC, 1, NR>(k, 0, off, adds, s, t, r);
+    if (live) store_row<DT, VEC, 1, NR>(k, 0, off, img * k.gin_extra, adds, s, t, r);
 }
 
 // =============================================================================
@@ -392,7 +412,7 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
     const uint32_t base = blockIdx.x * (nthr * U) + threadIdx.x;
     const uint32_t nvec = k.total;                      // vectors in the tensor
     bool live[U];
-    uint32_t offs[U], nfirst[U];
+    uint32_t offs[U], nfirst[U], imgs[U];
     int32_t cs[U];
     Raw<DT, VEC> ar[U], gr[U];
 #pragma unroll
@@ -411,9 +431,10 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
             plane = fdiv(fdiv(i, k.div_wv), k.div_h);  // i / (W / VEC) / H
             nfirst[u] = VEC;
         }
-        cs[u] = (int32_t)(plane - fdiv(plane, k.div_c) * (uint32_t)k.C);
-        ar[u] = load_raw<DT, VEC, true>(k.a, offs[u]);
-        gr[u] = load_raw<DT, VEC, true>(k.g_out, offs[u]);
+        imgs[u] = fdiv(plane, k.div_c);  // a vector lies in one image (checked at launch when the tensors are slices)
+        cs[u] = (int32_t)(plane - imgs[u] * (uint32_t)k.C);
+        ar[u] = load_raw<DT, VEC, true>(k.a, audited(k, 0, 2, offs[u] + imgs[u] * k.a_extra, VEC));
+        gr[u] = load_raw<DT, VEC, true>(k.g_out, audited(k, 1, 16, offs[u] + imgs[u] * k.gout_extra, VEC));
     }
     float x[U][VEC], t[U][VEC], r[NR ? NR : 1][U][VEC], s[U][VEC];
 #pragma unroll
@@ -425,7 +446,7 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
                                 : ew_sweep_impl<DT, VEC, U, false, NR, false>(k, cs, offs, x, t, r, nfirst, 0, k.n_ew);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (live[u]) store_row<DT, VEC, U, NR>(k, u, offs[u], adds, s[u], t, r);
+        if (live[u]) store_row<DT, VEC, U, NR>(k, u, offs[u], imgs[u] * k.gin_extra, adds, s[u], t, r);
 }
 
 // =============================================================================
@@ -455,8 +476,9 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
                               (plane * (uint32_t)k.H + 2 * oh + 1) * (uint32_t)k.W + cv * VEC};
     const uint32_t out_off = rowo * (uint32_t)k.Wo + cv * NO;  // Wo = W / 2: NO outputs of row oh
 
-    const Raw<DT, VEC> a0 = load_raw<DT, VEC, true>(k.a, offs[0]), a1 = load_raw<DT, VEC, true>(k.a, offs[1]);
-    const Raw<DT, NO> gr = load_raw<DT, NO, true>(k.g_out, out_off);
+    const uint32_t ash = img * k.a_extra;
+    const Raw<DT, VEC> a0 = load_raw<DT, VEC, true>(k.a, audited(k, 0, 3, offs[0] + ash, VEC)), a1 = load_raw<DT, VEC, true>(k.a, audited(k, 0, 4, offs[1] + ash, VEC));
+    const Raw<DT, NO> gr = load_raw<DT, NO, true>(k.g_out, audited(k, 1, 17, out_off + img * k.gout_extra, NO));
     float x[2][VEC], t[2][VEC], r[NR ? NR : 1][2][VEC], g[NO];
     unpack<DT, VEC>(a0, x[0]);
     unpack<DT, VEC>(a1, x[1]);
@@ -494,8 +516,8 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
         }
     }
     if (!live) return;
-    store_row<DT, VEC, 2, NR>(k, 0, offs[0], adds, s[0], t, r);
-    store_row<DT, VEC, 2, NR>(k, 1, offs[1], adds, s[1], t, r);
+    store_row<DT, VEC, 2, NR>(k, 0, offs[0], img * k.gin_extra, adds, s[0], t, r);
+    store_row<DT, VEC, 2, NR>(k, 1, offs[1], img * k.gin_extra, adds, s[1], t, r);
 }
 
 // =============================================================================
@@ -558,7 +580,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
         for (int j = 0; j < N; ++j) {
             offs[j] = plane_off + (uint32_t)(min(max(first + j, 0), k.H - 1) * k.W + col0);  // outside the plane: a safe row, replaced below
             cs[j] = L.c;
-            raw[j] = load_raw<DT, VEC, true>(k.a, offs[j]);
+            raw[j] = load_raw<DT, VEC, true>(k.a, audited(k, 0, 5, offs[j] + L.img * k.a_extra, VEC));
         }
 #pragma unroll
         for (int j = 0; j < N; ++j) unpack<DT, VEC>(raw[j], xs[j]);
@@ -585,7 +607,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
         // upstream gradients of the lane's windows of this row; windows that do not exist give nothing
         const bool row_ok = oh >= 0 && oh < k.Ho;
         float g[VO];
-        unpack<DT, VO>(load_raw<DT, VO>(k.g_out, oplane + (uint32_t)(min(max(oh, 0), k.Ho - 1) * k.Wo + L.j * VO)), g);
+        unpack<DT, VO>(load_raw<DT, VO>(k.g_out, audited(k, 1, 18, L.img * k.gout_extra + oplane + (uint32_t)(min(max(oh, 0), k.Ho - 1) * k.Wo + L.j * VO), VO)), g);
 #pragma unroll
         for (int e = 0; e < VO; ++e) g[e] = row_ok ? g[e] : 0.0f;
         if constexpr (MAX) {
@@ -671,7 +693,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
         for (int d = 0; d < S; ++d) {
             const int32_t row = hA + d;
             if (L.live && row >= r_lo && row < r_hi)
-                store_row<DT, VEC, K, NR>(k, d, plane_off + (uint32_t)(row * k.W + col0), adds, s[d], t, r);
+                store_row<DT, VEC, K, NR>(k, d, plane_off + (uint32_t)(row * k.W + col0), L.img * k.gin_extra, adds, s[d], t, r);
         }
 #pragma unroll
         for (int d = 0; d < KEEP; ++d) {
@@ -712,7 +734,7 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
     const uint32_t off = pix * (uint32_t)k.C + (uint32_t)c0;  // < N*H*W*C: i < total, or 0
 
     float x[1][VEC], t[1][VEC], r[NR ? NR : 1][1][VEC];
-    unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, off), x[0]);
+    unpack<DT, VEC>(load_raw<DT, VEC, true>(k.a, audited(k, 0, 6, off + pix * k.a_extra, VEC)), x[0]);
     const uint32_t offs[1] = {off};
     const int32_t cs[1] = {c0};
     const int32_t adds = ew_sweep<DT, VEC, 1, true, NR>(k, cs, offs, x, t, r);
@@ -720,7 +742,7 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
     float s[VEC];
     const PoolK &p = k.pool;
     if (p.kind == 0) {
-        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.g_out, off), s);
+        unpack<DT, VEC>(load_raw<DT, VEC, true>(k.g_out, audited(k, 1, 19, off + pix * k.gout_extra, VEC)), s);
     } else {
         const bool is_max = p.kind == OP_MAXPOOL;
         // windows (oh, ow) that hold the pixel
@@ -739,9 +761,9 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
 #pragma unroll
                 for (int b = 0; b < NOW; ++b) {
                     // windows beyond the range are read at a clamped (valid) pixel and not used
-                    const uint32_t o = (obase + (uint32_t)(min(oh_lo + a, k.Ho - 1) * k.Wo + min(ow_lo + b, k.Wo - 1))) * (uint32_t)k.C +
-                                       (uint32_t)c0;
-                    graw[a][b] = load_raw<DT, VEC>(k.g_out, o);
+                    const uint32_t opix = obase + (uint32_t)(min(oh_lo + a, k.Ho - 1) * k.Wo + min(ow_lo + b, k.Wo - 1));
+                    const uint32_t o = opix * (uint32_t)k.C + (uint32_t)c0;
+                    graw[a][b] = load_raw<DT, VEC>(k.g_out, audited(k, 1, 20, o + opix * k.gout_extra, VEC));
                     if (is_max) load_picks<VEC>(k.idx, o, pick[a][b]);
                 }
 #pragma unroll
@@ -765,9 +787,10 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
         for (int32_t oh = oh_lo; oh <= oh_hi; ++oh)
             for (int32_t ow = ow_lo; ow <= ow_hi; ++ow) {
                 // 0 <= oh < Ho, 0 <= ow < Wo: an output pixel; its VEC channels c0 .. c0 + VEC - 1
-                const uint32_t o = (obase + (uint32_t)(oh * k.Wo + ow)) * (uint32_t)k.C + (uint32_t)c0;
+                const uint32_t opix = obase + (uint32_t)(oh * k.Wo + ow);
+                const uint32_t o = opix * (uint32_t)k.C + (uint32_t)c0;
                 float g[VEC];
-                unpack<DT, VEC>(load_raw<DT, VEC>(k.g_out, o), g);
+                unpack<DT, VEC>(load_raw<DT, VEC>(k.g_out, audited(k, 1, 21, o + opix * k.gout_extra, VEC)), g);
                 if (is_max) {
                     int32_t pick[VEC];
                     load_picks<VEC>(k.idx, o, pick);
@@ -780,7 +803,7 @@ __global__ __launch_bounds__(256) void bwd_stage_nhwc_kernel(const BwdK k)
                 }
             }
     }
-    if (live) store_row<DT, VEC, 1, NR>(k, 0, off, adds, s, t, r);
+    if (live) store_row<DT, VEC, 1, NR>(k, 0, off, pix * k.gin_extra, adds, s, t, r);
 }
 
 // Disjoint 2 x 2 windows that tile the plane, channels-last: a lane owns VEC channels of one
@@ -805,10 +828,11 @@ __global__ __launch_bounds__(256) void bwd_direct2_nhwc_kernel(const BwdK k)
                               (p00 + (uint32_t)k.W + 1) * (uint32_t)k.C + (uint32_t)c0};
     const uint32_t out_off = opix * (uint32_t)k.C + (uint32_t)c0;
 
+    const uint32_t pixels[4] = {p00, p00 + 1, p00 + (uint32_t)k.W, p00 + (uint32_t)k.W + 1};
     Raw<DT, VEC> raw[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) raw[j] = load_raw<DT, VEC, true>(k.a, offs[j]);
-    const Raw<DT, VEC> gr = load_raw<DT, VEC, true>(k.g_out, out_off);
+    for (int j = 0; j < 4; ++j) raw[j] = load_raw<DT, VEC, true>(k.a, audited(k, 0, 7, offs[j] + pixels[j] * k.a_extra, VEC));
+    const Raw<DT, VEC> gr = load_raw<DT, VEC, true>(k.g_out, audited(k, 1, 22, out_off + opix * k.gout_extra, VEC));
     float x[4][VEC], t[4][VEC], r[NR ? NR : 1][4][VEC], g[VEC];
 #pragma unroll
     for (int j = 0; j < 4; ++j) unpack<DT, VEC>(raw[j], x[j]);
@@ -841,7 +865,7 @@ __global__ __launch_bounds__(256) void bwd_direct2_nhwc_kernel(const BwdK k)
     }
     if (!live) return;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) store_row<DT, VEC, 4, NR>(k, j, offs[j], adds, s[j], t, r);
+    for (int j = 0; j < 4; ++j) store_row<DT, VEC, 4, NR>(k, j, offs[j], pixels[j] * k.gin_extra, adds, s[j], t, r);
 }
 
 static void set_error(hipError_t e) { set_hip_error((int32_t)e); }
@@ -916,6 +940,8 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         }
         return BS_OK;
     }
+    if (k.flat && (k.a_extra || k.gin_extra || k.gout_extra) && ((int64_t)k.C * k.H * k.W) % vec != 0)
+        return BS_ERR_UNSUPPORTED;  // a vector would run from one image of a slice into the next
     if (k.flat) {
         // vectors that run over plane boundaries: no pooling, whole vectors, a plane of at least one vector
         if (k.pool.kind != 0 || vec != full || (int64_t)k.div_w.d != (int64_t)k.H * k.W || (int64_t)k.H * k.W < vec ||

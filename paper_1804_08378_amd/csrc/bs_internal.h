@@ -150,6 +150,15 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
                           uint32_t in_extra, uint32_t out_extra, const void *const *res,
                           int32_t *const *idx, void *stream);
 void set_hip_error(int32_t e);
+// bs_run.cpp: the bytes of a tensor of `images` images of `image_bytes` each, `stride_bytes` apart (a channel slice
+// when the stride exceeds the image), how the strided entry points validate one, and whether two share a byte
+// (exact for dense tensors; never "no" for overlapping ones)
+struct TensorBytes {
+    const void *p;
+    uint64_t images, image_bytes, stride_bytes;
+};
+bs_status resolve_slice(const bs_stack *stack, const int64_t *shape, const void *p, int64_t &stride, TensorBytes &out);
+bool tensors_overlap(const TensorBytes &a, const TensorBytes &b);
 // bs_run.cpp: resolve the address of the library's static scratch array on `device` (the current one)
 bs_status static_workspace_prepare(int device);
 // bs_nhwc.hip: channels-last kernels (element-wise, and one pooling step per sequence)

@@ -275,6 +275,13 @@ struct BwdK {
     // owns one column block and walks down a chunk of rows with the rows of the current windows in registers; max
     // pooling: it finds every window's pick itself (idx unused); gradients that belong to its neighbours' columns
     // travel inside the wave.  A wave holds spw = 64 / cbs (plane, chunk) segments of cbs lanes; a chunk is rc window rows.
+    // The stage input, the gradient with respect to it and the upstream gradient may be channel slices of larger
+    // tensors (first stage / last stage of bs_stack_backward_strided).  Row-major: elements every image starts later
+    // than in a dense tensor, for each image before it; channels-last: elements to skip per pixel beyond the C channels.
+    uint32_t a_extra, gin_extra, gout_extra;
+    // audit builds (-DBS_BWD_AUDIT): elements reachable from a / g_out / g_in, and where offsets beyond them are counted
+    uint32_t audit_lim[3];
+    uint32_t *audit;
     int32_t wave_rows;
     int32_t n_post;       // wave_rows, max pooling: element-wise operations (no Add) that follow the pooling, ew[n_ew .. n_ew + n_post):
                           // g_out is the gradient with respect to their output

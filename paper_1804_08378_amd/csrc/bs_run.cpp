@@ -199,6 +199,40 @@ bs_status run(const bs_stack *stack, const void *in, int64_t in_stride, const vo
 
 }  // namespace
 
+namespace bs {
+
+// A tensor of `shape` (N, C, H, W) that may be a channel slice of a larger one in the plan's layout: resolves the
+// batch stride (elements; 0 -> dense), checks it as bs_stack_run_strided does and describes the bytes it covers.
+bs_status resolve_slice(const bs_stack *stack, const int64_t *shape, const void *p, int64_t &stride, TensorBytes &out)
+{
+    const uint64_t es = dtype_size(stack->dtype);
+    const uint64_t images = (uint64_t)shape[0], image = numel(shape) / images;
+    if (stride == 0) stride = (int64_t)image;
+    if (stride < (int64_t)image || stride > 0x7fffffffll) return BS_ERR_SHAPE;
+    if (!aligned16(p)) return BS_ERR_ALIGN;
+    out = TensorBytes{p, images, image * es, (uint64_t)stride * es};
+    const bool dense = stride == (int64_t)image;
+    if (stack->opts.layout == BS_LAYOUT_NHWC) {
+        const int64_t hw = shape[2] * shape[3];
+        if (stride % hw != 0) return BS_ERR_SHAPE;
+        if (!dense && (uint64_t)(stride / hw) * es % 16 != 0) return BS_ERR_ALIGN;
+        if ((uint64_t)stride * images > 0x7fffffffull) return BS_ERR_SHAPE;
+        // the bytes of a channels-last slice's image: from its first pixel to the slice's channels of its last pixel
+        if (!dense) out.image_bytes = ((uint64_t)(hw - 1) * ((uint64_t)stride / (uint64_t)hw) + (uint64_t)shape[1]) * es;
+    } else if (!dense && out.stride_bytes % 16 != 0) {
+        return BS_ERR_ALIGN;
+    }
+    return BS_OK;
+}
+
+bool tensors_overlap(const TensorBytes &a, const TensorBytes &b)
+{
+    return spans_overlap(Span{a.p, a.images, a.image_bytes, a.stride_bytes}, Span{b.p, b.images, b.image_bytes, b.stride_bytes});
+}
+
+}  // namespace bs
+
+
 extern "C" bs_status bs_stack_run(const bs_stack *stack, const void *in, const void *const *residuals,
                                   void *out, int32_t *const *indices, void *workspace,
                                   uint64_t workspace_bytes, void *stream)

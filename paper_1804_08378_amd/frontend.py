@@ -140,28 +140,33 @@ class _StackFunction(torch.autograd.Function):
     when comparing the two)."""
 
     @staticmethod
-    def forward(ctx, module, nhwc, x, *residuals):
+    def forward(ctx, module, nhwc, stride, x, *residuals):
+        # x: dense in the plan's memory format, or (stride != 0) a channel slice that is read in place
         st = module.plan_for(x.shape, x.dtype, nhwc, keep_picks=True)
         mf = torch.channels_last if nhwc else torch.contiguous_format
         out = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf)
         # the last max pooling's picks, where the plan writes them, are kept for the backward pass
         # (saves recomputing them)
         picks = [torch.empty(sh, dtype=torch.int32, device=x.device, memory_format=mf) for sh in st.idx_shapes] or None
-        st.run_unchecked(x, list(residuals), out, 0, 0, picks)
+        st.run_unchecked(x, list(residuals), out, stride, 0, picks)
         ctx.save_for_backward(x, *residuals)
-        ctx.stack, ctx.mf, ctx.picks = st, mf, picks
+        ctx.stack, ctx.mf, ctx.picks, ctx.stride, ctx.nhwc = st, mf, picks, stride, nhwc
         return out
 
     @staticmethod
     def backward(ctx, grad_out):
         x, *residuals = ctx.saved_tensors
-        need = ctx.needs_input_grad  # (module, nhwc, x, *residuals)
+        need = ctx.needs_input_grad  # (module, nhwc, stride, x, *residuals)
         mf = ctx.mf
-        gx = torch.empty_like(x, memory_format=mf) if need[2] else None
-        gres = [torch.empty_like(r, memory_format=mf) if wanted else None for r, wanted in zip(residuals, need[3:])]
-        # operands validated in forward(); the upstream gradient has the output's shape and dtype
-        ctx.stack.backward_unchecked(x, residuals, grad_out.contiguous(memory_format=mf), gx, gres, ctx.picks)
-        return (None, None, gx, *gres)
+        gx = torch.empty(x.shape, dtype=x.dtype, device=x.device, memory_format=mf) if need[3] else None
+        gres = [torch.empty_like(r, memory_format=mf) if wanted else None for r, wanted in zip(residuals, need[4:])]
+        # operands validated in forward(); the upstream gradient has the output's shape and dtype and is
+        # read in place when it is dense or a channel slice (a gradient buffer's channel range)
+        gstride = BrainSlugStack._slice_stride(grad_out, ctx.stack.out_shape, x, ctx.nhwc)
+        if gstride is None:
+            grad_out, gstride = grad_out.contiguous(memory_format=mf), 0
+        ctx.stack.backward_unchecked(x, residuals, grad_out, gx, gres, ctx.picks, ctx.stride, gstride, 0)
+        return (None, None, None, gx, *gres)
 
 
 class BrainSlugStack(nn.Module):
@@ -295,37 +300,25 @@ class BrainSlugStack(nn.Module):
         if self.channels is not None and x.shape[1] != self.channels:
             raise RuntimeError(f"expected {self.channels} channels, got {x.shape[1]}")
         if torch.is_grad_enabled() and (x.requires_grad or any(r.requires_grad for r in residuals)):
-            # recorded by autograd: dense operands in the input's memory format (the backward pass
-            # has no channel-slice kernels: slices are copied), a new output tensor (`out` is not used)
+            # recorded by autograd: the input dense in its memory format or a channel slice of a
+            # concatenation buffer (read in place, forward and backward), dense residual operands, a
+            # new output tensor (`out` is not used)
             if len(residuals) != self.n_residuals:
                 raise RuntimeError(f"stack has {self.n_residuals} Add layers, got {len(residuals)} residual tensors")
-            nhwc = not x.is_contiguous() and x.is_contiguous(memory_format=torch.channels_last)
+            x, stride, nhwc = self._input_slice(x)
             mf = torch.channels_last if nhwc else torch.contiguous_format
             st = self.plan_for(x.shape, x.dtype, nhwc, keep_picks=True)
             for r, want in zip(residuals, st.res_shapes):
                 if r.shape != want or r.dtype != x.dtype or r.device != x.device:
                     raise RuntimeError(f"residual operand of shape {tuple(r.shape)} / {r.dtype}: the Add layer "
                                        f"needs {tuple(want)} / {x.dtype} on the input's device (no broadcasting)")
-            return _StackFunction.apply(self, nhwc, x.contiguous(memory_format=mf),
-                                        *[r.contiguous(memory_format=mf) for r in residuals])
+            return _StackFunction.apply(self, nhwc, stride, x, *[r.contiguous(memory_format=mf) for r in residuals])
         with torch.no_grad():
             # a channels_last tensor stays channels_last: the stack is planned for that memory
             # order and its output is channels_last as well (what the convolutions around it use)
             # a channel slice of a concatenation buffer (of either memory format) is read in
             # place; other layouts are copied
-            stride, nhwc = 0, False
-            if not x.is_contiguous():
-                nhwc = x.is_contiguous(memory_format=torch.channels_last)
-                if not nhwc:
-                    es = x.element_size()
-                    stride = bs.batch_stride(x)
-                    if stride is None or (x.data_ptr() % 16) or (stride * es) % 16:
-                        stride = bs.batch_stride_nhwc(x)
-                        hw = x.shape[2] * x.shape[3]
-                        if stride is None or (x.data_ptr() % 16) or (stride // hw * es) % 16:
-                            x, stride = x.contiguous(), 0
-                        else:
-                            nhwc = True
+            x, stride, nhwc = self._input_slice(x)
             st = self._plans.get((x.shape, x.dtype, nhwc, False)) or self.plan_for(x.shape, x.dtype, nhwc)
             mf = torch.channels_last if nhwc else torch.contiguous_format
             if len(residuals) != self.n_residuals:
@@ -346,6 +339,25 @@ class BrainSlugStack(nn.Module):
                 out, ostride = torch.empty(st.out_shape, dtype=x.dtype, device=x.device, memory_format=mf), 0
             st.run_unchecked(x, res, out, stride, ostride)
         return out
+
+    @staticmethod
+    def _input_slice(x):
+        """(tensor, batch stride, channels-last?) to run on: `x` itself when it is dense in either memory
+        format (stride 0) or a channel slice of a dense tensor that can be read in place, else a dense copy."""
+        stride, nhwc = 0, False
+        if not x.is_contiguous():
+            nhwc = x.is_contiguous(memory_format=torch.channels_last)
+            if not nhwc:
+                es = x.element_size()
+                stride = bs.batch_stride(x)
+                if stride is None or (x.data_ptr() % 16) or (stride * es) % 16:
+                    stride = bs.batch_stride_nhwc(x)
+                    hw = x.shape[2] * x.shape[3]
+                    if stride is None or (x.data_ptr() % 16) or (stride // hw * es) % 16:
+                        x, stride = x.contiguous(), 0
+                    else:
+                        nhwc = True
+        return x, stride, nhwc
 
     @staticmethod
     def _slice_stride(t, shape, like, nhwc):

@@ -439,6 +439,69 @@ def test_forward_and_backward_can_be_captured_in_a_hip_graph_and_replayed():
     st.close()
 
 
+def _slice_stacks(c, h, w):
+    return {
+        "bn_add_relu": [wl.bn_params(c, 60), wl.add(), wl.relu()],                                   # element-wise
+        "max2": [wl.bn_params(c, 61), wl.relu(), wl.maxpool(2, 2)],                                  # windows that tile the plane
+        "stem": [wl.bn_params(c, 62), wl.relu(), wl.maxpool(3, 2, 1)],                               # lanes walk the rows
+        "avg3s1": [wl.bn_params(c, 63), wl.relu(), wl.avgpool(3, 1, 1)],                             # gather, compiled window
+        "max5": [wl.relu(), wl.maxpool(5, 2, 2)],                                                    # gather, recorded picks
+        "halo_stress": [wl.bn_params(c, 64), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1), wl.bn_params(c, 65), wl.relu()],
+        "head": [wl.bn_params(c, 66), wl.relu(), wl.avgpool((h, w), (h, w), 0)],
+    }
+
+
+@pytest.mark.parametrize("layout", [bs.BS_LAYOUT_NCHW, bs.BS_LAYOUT_NHWC])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("shape", [(2, 8, 12, 16), (3, 16, 7, 7), (2, 8, 13, 11)])
+def test_gradients_of_channel_slices_are_read_and_written_in_place(shape, dtype, layout):
+    """bs_stack_backward_strided: the input, the upstream gradient and the input's gradient as channel
+    slices of larger tensors (eight channels on either side).  The same bits as the dense call, the oracle's
+    values, and nothing outside the slices touched (guard values in the gradient buffer, NaN around the inputs)."""
+    n, c, h, w = shape
+    td = TORCH[dtype]
+    mf = torch.channels_last if layout == bs.BS_LAYOUT_NHWC else torch.contiguous_format
+    stride_of = bs.batch_stride_nhwc if layout == bs.BS_LAYOUT_NHWC else bs.batch_stride
+    for name, layers in _slice_stacks(c, h, w).items():
+        print(f"[backward] slices/{name} shape={shape} dtype={dtype} layout={layout}", flush=True)
+        x, res, dy = _inputs(layers, shape, 11, dtype)
+        ref_x, ref_res = bw.backward_stack(layers, x, res, dy, dtype)
+        st = bs.Stack(layers, shape, dtype).plan(layout=layout).plan_backward()
+        put = lambda a: _dev(a, dtype).contiguous(memory_format=mf)
+        xd, dyd, resd = put(x), put(dy), [put(r) for r in res]
+        dense_gx, dense_gres = st.backward(xd, resd, dyd)
+        big = lambda t, fill: torch.full((n, t.shape[1] + 16) + tuple(t.shape[2:]), fill, dtype=td, device="cuda").contiguous(memory_format=mf)
+        big_x, big_dy, guard = big(xd, float("nan")), big(dyd, float("nan")), 4321.0
+        big_gx = big(xd, guard)
+        big_x[:, 8:8 + c] = xd
+        big_dy[:, 8:8 + c] = dyd
+        xs, dys, gxs = big_x[:, 8:8 + c], big_dy[:, 8:8 + c], big_gx[:, 8:8 + c]
+        gres = [torch.empty_like(r) for r in resd]
+        ws = st.workspace("cuda", backward=True)
+        nws = bs.bs_stack_backward_workspace_bytes(st.handle)
+        bs.bs_stack_backward_strided(st.handle, xs.data_ptr(), stride_of(xs), [r.data_ptr() for r in resd], None, dys.data_ptr(),
+                                     stride_of(dys), gxs.data_ptr(), stride_of(gxs), [g.data_ptr() for g in gres],
+                                     ws.data_ptr() if nws else 0, nws, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(gxs, dense_gx), name
+        for a, b in zip(gres, dense_gres):
+            assert torch.equal(a, b), name
+        _close(gxs.float().cpu().numpy(), ref_x, dtype, f"slices/{name} grad_x")
+        assert bool((big_gx[:, :8] == guard).all()) and bool((big_gx[:, 8 + c:] == guard).all()), name
+        # strides that are no channel slice, and outputs over inputs, are refused
+        with pytest.raises(bs.BrainSlugError) as e:
+            bs.bs_stack_backward_strided(st.handle, xs.data_ptr(), c * h * w - 8, [r.data_ptr() for r in resd], None, dys.data_ptr(),
+                                         stride_of(dys), gxs.data_ptr(), stride_of(gxs), [g.data_ptr() for g in gres],
+                                         ws.data_ptr() if nws else 0, nws, 0)
+        assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_SHAPE"]
+        with pytest.raises(bs.BrainSlugError) as e:
+            bs.bs_stack_backward_strided(st.handle, xs.data_ptr(), stride_of(xs), [r.data_ptr() for r in resd], None, dys.data_ptr(),
+                                         stride_of(dys), xs.data_ptr(), stride_of(xs), [g.data_ptr() for g in gres],
+                                         ws.data_ptr() if nws else 0, nws, 0)
+        assert e.value.status == bs.STATUS_BY_NAME["BS_ERR_ALIAS"]
+        st.close()
+
+
 def test_repeated_calls_give_identical_bits():
     """A gather has one summation order: two runs agree bit for bit (no atomics anywhere)."""
     layers = _stacks(6)["halo_stress"]
