@@ -200,7 +200,9 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
             if (nhwc) {
                 // a lane per pixel (per window when 2 x 2 windows tile the plane) and channel vector
                 g.vec = g.k.C % full == 0 ? full : 1;
-                g.k.direct = tiles2x2 && g.vec == full;
+                // (with two or more Adds in the stage the window-owning kernel would keep 4 pixels x vec channels of
+                // every residual's factors in registers and spill: those stages gather with recorded picks)
+                g.k.direct = tiles2x2 && g.vec == full && g.n_res <= 1;
                 lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 4 : 1);
                 g.k.div_wv = make_fastdiv((uint32_t)(g.k.C / g.vec));
                 g.k.div_w = make_fastdiv((uint32_t)(g.k.direct ? g.k.Wo : g.k.W));

@@ -912,14 +912,14 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         if (k.direct && ((p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 2 || p.kw != 2 || p.sh != 2 || p.sw != 2 ||
                          p.ph != 0 || p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo))
             return BS_ERR_UNSUPPORTED;
+        if (k.direct && n_add > 1) return BS_ERR_UNSUPPORTED;  // planned for the gathering kernel instead
         if (!k.direct && p.kind == OP_MAXPOOL && !k.idx) return BS_ERR_NULL;
         // windows over one pixel: at most ceil(kh / sh) x ceil(kw / sw); 2 x 2 and 3 x 3 are compiled in
         const int32_t noh = p.kind != 0 ? (p.kh + p.sh - 1) / p.sh : 0, now = p.kind != 0 ? (p.kw + p.sw - 1) / p.sw : 0;
 #define BS_LAUNCH_NHWC(DT, V)                                                          \
     do {                                                                               \
         if (k.direct && n_add == 0) bwd_direct2_nhwc_kernel<DT, V, 0><<<g, b, 0, st>>>(k); \
-        else if (k.direct && n_add == 1) bwd_direct2_nhwc_kernel<DT, V, 1><<<g, b, 0, st>>>(k); \
-        else if (k.direct) bwd_direct2_nhwc_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k); \
+        else if (k.direct) bwd_direct2_nhwc_kernel<DT, V, 1><<<g, b, 0, st>>>(k); \
         else if (noh == 2 && now == 2 && n_add == 0) bwd_stage_nhwc_kernel<DT, V, 2, 2, 0><<<g, b, 0, st>>>(k); \
         else if (noh == 2 && now == 2) bwd_stage_nhwc_kernel<DT, V, 2, 2><<<g, b, 0, st>>>(k); \
         else if (noh == 3 && now == 3 && n_add == 0) bwd_stage_nhwc_kernel<DT, V, 3, 3, 0><<<g, b, 0, st>>>(k); \

@@ -838,6 +838,27 @@ def test_stack_under_autograd_keeps_only_its_operands():
     with torch.no_grad():
         assert not stack(x).requires_grad
     assert not stack(x.detach()).requires_grad
+    # a channel slice of a larger tensor as input, a channel slice of the output's gradient: both are read in
+    # place (bs_stack_backward_strided), the gradient of the larger tensor is that of the slice
+    seen = []
+    plain = bs.Stack.backward_unchecked
+    def spy(self, *a, **k):
+        seen.append((a[6] if len(a) > 6 else k.get("in_batch_stride", 0), a[7] if len(a) > 7 else k.get("grad_out_batch_stride", 0)))
+        return plain(self, *a, **k)
+    bs.Stack.backward_unchecked = spy
+    try:
+        for mf in (torch.contiguous_format, torch.channels_last):
+            big = torch.randn(2, 24, 16, 16, device="cuda").contiguous(memory_format=mf).requires_grad_(True)
+            w = torch.randn(2, 16, 8, 8, device="cuda").contiguous(memory_format=mf)
+            y = torch.cat([stack(big[:, 8:16]), torch.zeros(2, 8, 8, 8, device="cuda")], 1)
+            (y * w).sum().backward()
+            big2 = big.detach().clone().requires_grad_(True)
+            (torch.cat([reference(big2[:, 8:16]), torch.zeros(2, 8, 8, 8, device="cuda")], 1) * w).sum().backward()
+            assert (big.grad - big2.grad).abs().max().item() <= 1e-5 * big2.grad.abs().max().item()
+            assert bool((big.grad[:, :8] == 0).all()) and bool((big.grad[:, 16:] == 0).all())
+        assert len(seen) == 2 and all(s[0] > 0 for s in seen), seen
+    finally:
+        bs.Stack.backward_unchecked = plain
     stack.close()
 
 
