@@ -710,7 +710,7 @@ def main():
     if args.nhwc:
         stacks = None
         torch.cuda.empty_cache()
-        log("channels-last (NHWC) plans: one step per sequence")
+        log("channels-last (NHWC) plans: one step per sequence, or two pooling steps in one tile kernel")
         log(f"{'config':<16}{'dtype':<6}{'sequences':<24}{'MB':>8}{'us mean':>9}{'us min':>8}{'GB/s':>8}{'%peak':>7}"
             f"{'lbl us':>9}{'speedup':>8}")
         rows = []

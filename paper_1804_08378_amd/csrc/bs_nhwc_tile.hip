@@ -353,8 +353,12 @@ BS_DEV TilePlace tile_place(const NhwcTile2K &k, uint32_t t)
     return tp;
 }
 
+// Waves per SIMD the register allocator is held to: one more than it would choose by itself where that costs no
+// scratch memory; a second pooling step with stride 1 keeps a 4 x 4 block of cells per lane and gets one wave less.
+constexpr int tile_waves(int dt, int k2, int s2) { return (dt == DT_F32 ? 4 : 3) - (k2 == 3 && s2 == 1 ? 1 : 0); }
+
 template <int DT, int VEC, int K1, int S1, int K2, int S2>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DT == DT_F32 ? 4 : 3, DT == DT_F32 ? 4 : 3))) void nhwc_tile2_kernel(const NhwcTile2K k)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(tile_waves(DT, K2, S2), tile_waves(DT, K2, S2)))) void nhwc_tile2_kernel(const NhwcTile2K k)
 {
     extern __shared__ uint4 lds[];
     uint4 *lds0 = lds, *lds1 = lds + k.lds1_off;
