@@ -33,11 +33,6 @@ namespace {
 inline uint64_t numel(const int64_t *sh) { return (uint64_t)sh[0] * sh[1] * sh[2] * sh[3]; }
 inline uint64_t align256(uint64_t v) { return (v + 255u) & ~(uint64_t)255u; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline bool overlap(const void *a, uint64_t na, const void *b, uint64_t nb)
-{
-    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-    return x < y + nb && y < x + na;
-}
 
 // The stage's layers as a forward stack of their own, planned with the stack's options.
 bs_status make_forward(const bs_stack *s, BwdStage &g, bool host_only)
@@ -85,6 +80,18 @@ bool walks_rows(const bs_stack *s, const BwdStage &g)
     return s->opts.layout != BS_LAYOUT_NHWC && s->opts.lane_exchange >= 0 &&
            (p.kind == OP_MAXPOOL || (p.kind == OP_AVGSUM && p.sh == 2)) && p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && g.k.W % full == 0 &&
            g.k.W / full <= 64 && g.k.Wo * p.sw == g.k.W && g.k.Ho == (g.k.H + 2 - 3) / p.sh + 1;
+}
+
+// Stage g = [element-wise list without Add, average pooling 3 x 3 / 1 / 1 that keeps the plane's size] and the stage
+// behind it = [max pooling 3 x 3 / 2 / 1 alone, with the element-wise operations that joined it]: one kernel walks
+// both levels down the plane (rows of whole 4-cell blocks that fit one wave).
+bool walks_two_levels(const bs_stack *s, const BwdStage &g, const BwdStage &nx)
+{
+    const PoolK &p = g.k.pool, &q = nx.k.pool;
+    return s->opts.layout != BS_LAYOUT_NHWC && s->opts.lane_exchange >= 0 && g.n_res == 0 && nx.n_res == 0 && g.k.n_post == 0 &&
+           nx.k.n_ew == 0 && g.k.n_ew + nx.k.n_post <= K_BWD_EW && p.kind == OP_AVGSUM && p.kh == 3 && p.kw == 3 && p.sh == 1 &&
+           p.sw == 1 && p.ph == 1 && p.pw == 1 && g.k.Ho == g.k.H && g.k.Wo == g.k.W && q.kind == OP_MAXPOOL && q.sh == 2 &&
+           walks_rows(s, nx) && g.k.W % 4 == 0 && g.k.W / 4 <= 64;
 }
 
 }  // namespace
@@ -184,6 +191,24 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
             plan->stages.erase(plan->stages.begin() + (long)j + 1);
         }
 
+        // an average pooling stage in front of such a max pooling stage: both in one kernel, the plane between
+        // them (and its gradient) only in registers
+        for (size_t j = 0; j + 1 < plan->stages.size(); ++j) {
+            BwdStage &g = plan->stages[j];
+            const BwdStage &nx = plan->stages[j + 1];
+            if (!walks_two_levels(stack, g, nx)) continue;
+            for (int32_t q = 0; q < nx.k.n_post; ++q) g.k.ew[g.k.n_ew + q] = nx.k.ew[q];
+            g.k.n_post = nx.k.n_post;
+            g.k.pool2 = nx.k.pool;
+            g.k.wave_rows = 2;
+            g.k.Ho = nx.k.Ho;
+            g.k.Wo = nx.k.Wo;
+            g.idx_slot = -1;
+            g.n_layers += nx.n_layers;
+            std::memcpy(g.out_shape, nx.out_shape, sizeof g.out_shape);
+            plan->stages.erase(plan->stages.begin() + (long)j + 1);
+        }
+
         // ---- launch geometry, forward stacks, workspace
         const uint64_t es = dtype_size(stack->dtype);
         const int32_t full = stack->dtype == BS_F32 ? 4 : 8;
@@ -221,6 +246,24 @@ extern "C" bs_status bs_stack_plan_backward(bs_stack *stack)
                 }
                 lanes = numel(g.in_shape) / (uint64_t)g.vec / (g.k.direct ? 2 : 1);
                 g.k.div_wv = make_fastdiv((uint32_t)(g.k.flat ? 1 : g.k.W / g.vec));
+                if (g.k.wave_rows == 2) {
+                    // two pooling levels in one kernel: 4 cells per lane whatever the element size (registers)
+                    BwdK &k = g.k;
+                    g.vec = 4;
+                    k.div_wv = make_fastdiv((uint32_t)(k.W / 4));
+                    k.cbs = k.W / 4;
+                    k.spw = 64 / k.cbs;
+                    const int64_t planes = g.in_shape[0] * g.in_shape[1];
+                    const int32_t rows = (k.H + 1) / 2;  // window rows of the max pooling that cover the plane's rows
+                    int32_t rc = std::min(K_BWD_ROWS2_RC, rows);
+                    k.chunks = (rows + rc - 1) / rc;
+                    k.rc = (rows + k.chunks - 1) / k.chunks;
+                    k.chunks = (rows + k.rc - 1) / k.rc;
+                    k.units = (uint32_t)(planes * k.chunks);
+                    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+                    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+                    lanes = (uint64_t)k.units * (uint64_t)k.cbs;
+                } else
                 // overlapping 3 x 3 windows on rows that fit one wave: the kernel whose lanes walk down the rows
                 if (walks_rows(stack, g) && g.vec == full) {
                     BwdK &k = g.k;

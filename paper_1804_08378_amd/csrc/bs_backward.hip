@@ -711,6 +711,200 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
 }
 
 // =============================================================================
+// bwd_rows2_kernel: two stages in one kernel -- element-wise list, average pooling 3 x 3 (stride 1,
+// padding 1), then max pooling 3 x 3 (stride 2, padding 1) with element-wise operations behind it
+// (the stacked pooling of Section 4.4 with its activation) -- on planes whose rows fit one wave.
+// The stack's input and the upstream gradient are read once and the input gradient is written
+// once; nothing is recomputed by another kernel and nothing passes through the workspace.
+//
+// As in bwd_rows_kernel the lanes of a row sit side by side in one wave and walk down a chunk of
+// rows; per window row `oh` of the max pooling a lane
+//   1. reads two new input rows (2 oh + 1, 2 oh + 2), applies the leading list (values y, derivative T),
+//   2. forms the two new rows (2 oh, 2 oh + 1) of the average pooling's output `a` in the forward
+//      kernels' arithmetic (row-major sum from +0, times the divisor's reciprocal, rounded to storage),
+//   3. finds the picks of its max windows over a rows 2 oh - 1 .. 2 oh + 1, scales the upstream
+//      gradients by the trailing list's derivative at the maxima and adds them to the picked cells
+//      (sums per a row; a pick in the left neighbour's column travels there by a lane shift),
+//   4. a rows 2 oh - 1 and 2 oh can get nothing more: their gradients, times the reciprocal of the
+//      average's divisor, become rows of `w` (with the neighbours' edge columns),
+//   5. writes the input gradient of rows 2 oh - 2 and 2 oh - 1: the 3 x 3 sum of w around the cell,
+//      times T.
+// Rings: y rows 2 oh - 1 .. 2 oh + 2, T rows 2 oh - 2 .. 2 oh + 2, a rows 2 oh - 1 .. 2 oh + 1 and their
+// gradient sums, w rows 2 oh - 3 .. 2 oh.  A chunk of rc window rows writes input rows
+// [2 rc chunk, 2 rc (chunk + 1)) and visits window rows rc chunk - 1 .. rc (chunk + 1); every lane of
+// a wave runs the same number of iterations.  Sums have a fixed order: the same bits on every run.
+// The gradient between the two poolings stays in float32 registers (it is not rounded to the
+// storage type as it is between stages that run as separate kernels).
+// =============================================================================
+template <int DT, int VEC>
+__global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
+{
+    constexpr int K = 3, S = 2, VO = VEC / S;
+    constexpr int YW = VEC + 2, AW = VEC + 1;  // a row with both neighbours' edge columns / with the left one
+    static_assert(VEC % S == 0, "whole windows per lane");
+    const XLane L = xrows_lane(k);
+    const int32_t col0 = L.j * VEC;
+    const bool has_left = L.j > 0, has_right = L.j + 1 < k.cbs;
+    const uint32_t plane_off = L.plane * (uint32_t)(k.H * k.W), oplane = L.plane * (uint32_t)(k.Ho * k.Wo);
+    const int32_t r_lo = L.chunk * k.rc * S, r_hi = L.chunk + 1 == k.chunks ? k.H : min(r_lo + k.rc * S, k.H);
+    const int32_t oh_first = L.chunk * k.rc - 1;
+    const int32_t n_iter = max(k.rc, (k.H - (k.chunks - 1) * k.rc * S + S - 1) / S) + 2;  // the same for every lane
+
+    float yf[4][YW], T[5][VEC], af[3][AW], gt[3][VEC], wf[4][YW];
+    const int32_t cs1[1] = {L.c};
+
+    // rows [first, first + N) of the plane: leading element-wise list -> y with edge columns (padding +0: the
+    // average's) into yf[slot ..], derivative factors into T[tslot ..]
+    auto take_rows = [&](auto n_tag, int slot, int tslot, int32_t first) {
+        constexpr int N = decltype(n_tag)::value;
+        float xs[N][VEC], ts[N][VEC], none[1][N][VEC];
+        uint32_t offs[N];
+        int32_t cs[N];
+        Raw<DT, VEC> raw[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            offs[j] = plane_off + (uint32_t)(min(max(first + j, 0), k.H - 1) * k.W + col0);  // outside the plane: a safe row, replaced below
+            cs[j] = L.c;
+            raw[j] = load_raw<DT, VEC, true>(k.a, audited(k, 0, 30, offs[j] + L.img * k.a_extra, VEC));
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) unpack<DT, VEC>(raw[j], xs[j]);
+        ew_sweep<DT, VEC, N, false, 0>(k, cs, offs, xs, ts, none);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const bool ok = first + j >= 0 && first + j < k.H;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                xs[j][e] = ok ? xs[j][e] : 0.0f;
+                T[tslot + j][e] = ts[j][e];
+            }
+            with_neighbours<VEC, 1, 1>(xs[j], yf[slot + j], has_left, has_right, 0.0f);
+        }
+    };
+    // row `row` of the average pooling's output from y rows yf[slot .. slot + 2] -> af[aslot] (outside the
+    // plane: the max pooling's padding)
+    auto average_row = [&](int slot, int aslot, int32_t row) {
+        float v[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = xrows_window_sum<K, K, false, YW>(yf + slot, e);
+        xrows_normalise<DT, VEC, K, K, 1, 1, 1>(v, k.pool, row - 1, col0 - 1, k.H, k.W);
+        const bool ok = row >= 0 && row < k.H;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = ok ? v[e] : -INFINITY;
+        with_neighbours<VEC, 1, 0>(v, af[aslot], has_left, has_right, -INFINITY);
+    };
+
+#pragma unroll
+    for (int d = 0; d < 3; ++d)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) gt[d][e] = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int e = 0; e < YW; ++e) wf[d][e] = 0.0f;
+    // y rows 2 oh - 2 .. 2 oh of the first window row -> a row 2 oh - 1; y rows 2 oh - 1, 2 oh stay
+    take_rows(std::integral_constant<int, 3>{}, 0, 0, oh_first * S - 2);
+    average_row(0, 0, oh_first * S - 1);
+#pragma unroll
+    for (int e = 0; e < YW; ++e) {
+        yf[0][e] = yf[1][e];
+        yf[1][e] = yf[2][e];
+    }
+
+    for (int32_t it = 0; it < n_iter; ++it) {
+        const int32_t oh = oh_first + it, hA = oh * S - 1;  // a rows hA .. hA + 2 under this window row
+        take_rows(std::integral_constant<int, 2>{}, 2, 3, hA + 2);
+        // upstream gradients of the lane's windows of this row; windows that do not exist give nothing
+        const bool row_ok = oh >= 0 && oh < k.Ho;
+        float g[VO];
+        unpack<DT, VO>(load_raw<DT, VO>(k.g_out, audited(k, 1, 31, L.img * k.gout_extra + oplane + (uint32_t)(min(max(oh, 0), k.Ho - 1) * k.Wo + L.j * VO), VO)), g);
+#pragma unroll
+        for (int e = 0; e < VO; ++e) g[e] = row_ok ? g[e] : 0.0f;
+        average_row(0, 1, hA + 1);
+        average_row(1, 2, hA + 2);
+        // first maximum of every window: code = window row * K + window column
+        int32_t pick[VO];
+        float best[1][VO];
+#pragma unroll
+        for (int e = 0; e < VO; ++e) {
+            best[0][e] = -INFINITY;
+            pick[e] = -1;
+#pragma unroll
+            for (int dh = 0; dh < K; ++dh)
+#pragma unroll
+                for (int dw = 0; dw < K; ++dw) {
+                    const float v = af[dh][e * S + dw];
+                    const bool more = v > best[0][e];
+                    best[0][e] = more ? v : best[0][e];
+                    pick[e] = more ? dh * K + dw : pick[e];
+                }
+        }
+        // element-wise operations behind the max pooling: their derivative at the window's maximum
+        if (k.n_post > 0) {
+            float tp[1][VO], none[1][1][VO];
+            const uint32_t no_off[1] = {0}, all[1] = {VO};
+#pragma unroll
+            for (int e = 0; e < VO; ++e) best[0][e] = row_ok ? best[0][e] : 0.0f;  // windows that do not exist: any finite value
+            ew_sweep_impl<DT, VO, 1, false, 0, false>(k, cs1, no_off, best, tp, none, all, k.n_ew, k.n_post);
+#pragma unroll
+            for (int e = 0; e < VO; ++e) g[e] *= tp[0][e];
+        }
+        // gradients into the picked cells of the a rows, in the order a cell's windows have in the plane
+#pragma unroll
+        for (int dh = 0; dh < K; ++dh) {
+            const float to_left = pick[0] == dh * K ? g[0] : 0.0f;  // the first window's first column is the left lane's last
+            const float from_right = from_right_lane(to_left);
+#pragma unroll
+            for (int e = 0; e < VO; ++e)
+#pragma unroll
+                for (int dw = 0; dw < K; ++dw) {
+                    const int col = e * S + dw - 1;
+                    if (col >= 0 && col < VEC) gt[dh][col] += pick[e] == dh * K + dw ? g[e] : 0.0f;
+                }
+            gt[dh][VEC - 1] += has_right ? from_right : 0.0f;
+        }
+        // a rows hA and hA + 1 are complete: times the reciprocal of the average's divisor, with edge columns
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            const int32_t row = min(max(hA + d, 0), k.H - 1);  // rows outside the plane hold zeros
+            float w[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) w[e] = gt[d][e] * bwd_avg_inv(k.pool, k.H, k.W, row, col0 + e);
+            with_neighbours<VEC, 1, 1>(w, wf[2 + d], has_left, has_right, 0.0f);
+        }
+        // input rows hA - 1 and hA: every average window that holds the cell, row-major, times the list's derivative
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            const int32_t row = hA - 1 + d;
+            float v[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e] = xrows_window_sum<K, K, false, YW>(wf + d, e) * T[d][e];
+            if (L.live && row >= r_lo && row < r_hi && k.g_in)
+                store_elems<DT, VEC>(k.g_in, audited(k, 2, 32, plane_off + (uint32_t)(row * k.W + col0) + L.img * k.gin_extra, VEC), v);
+        }
+        // next window row: two rows down
+#pragma unroll
+        for (int e = 0; e < YW; ++e) {
+            yf[0][e] = yf[2][e];
+            yf[1][e] = yf[3][e];
+            wf[0][e] = wf[2][e];
+            wf[1][e] = wf[3][e];
+        }
+#pragma unroll
+        for (int e = 0; e < AW; ++e) af[0][e] = af[2][e];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            T[0][e] = T[2][e];
+            T[1][e] = T[3][e];
+            T[2][e] = T[4][e];
+            gt[0][e] = gt[2][e];
+            gt[1][e] = 0.0f;
+            gt[2][e] = 0.0f;
+        }
+    }
+}
+
+// =============================================================================
 // Channels-last tensors (N, H, W, C in memory).  A lane owns VEC consecutive channels of one
 // pixel: the same three steps as bwd_stage_kernel, with BatchNorm parameters as per-lane
 // vectors and a window's gradient and picks as one vector each (the VEC channels of the output
@@ -951,6 +1145,31 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
                (int64_t)k.div_h.d != (k.direct ? k.Ho : k.H) || (int64_t)k.div_c.d != k.C ||
                (int64_t)grid * threads < (int64_t)k.total) {
         return BS_ERR_UNSUPPORTED;
+    }
+    if (k.wave_rows == 2) {
+        // what the two-level kernel assumes: average 3 x 3 / 1 / 1 that keeps the plane's size, then max 3 x 3 / 2 / 1;
+        // no Add anywhere; 4 cells per lane; a row's column blocks in one wave; chunks that cover the plane
+        const PoolK &p = k.pool, &q = k.pool2;
+        for (int32_t j = 0; j < k.n_ew + k.n_post; ++j)
+            if (j >= K_BWD_EW || k.ew[j].kind == OP_ADD) return BS_ERR_UNSUPPORTED;
+        if (k.n_post < 0 || k.n_ew + k.n_post > K_BWD_EW) return BS_ERR_UNSUPPORTED;
+        if (k.direct || p.kind != OP_AVGSUM || p.kh != 3 || p.kw != 3 || p.ph != 1 || p.pw != 1 || p.sh != 1 || p.sw != 1 ||
+            q.kind != OP_MAXPOOL || q.kh != 3 || q.kw != 3 || q.ph != 1 || q.pw != 1 || q.sh != 2 || q.sw != 2 || vec != 4 ||
+            k.W % 4 != 0 || k.cbs != k.W / 4 || k.cbs < 1 || k.cbs > 64 || k.spw != 64 / k.cbs || k.Wo * 2 != k.W ||
+            k.Ho != (k.H + 2 - 3) / 2 + 1 || k.rc < 1 || k.chunks < 1 || (int64_t)(k.chunks - 1) * k.rc * 2 >= k.H ||
+            (int64_t)k.div_cbs.d != k.cbs || (int64_t)k.div_chunks.d != k.chunks || (int64_t)k.div_c.d != k.C ||
+            (uint64_t)grid * 4 * k.spw < k.units)
+            return BS_ERR_UNSUPPORTED;
+        if (dtype == BS_F32) bwd_rows2_kernel<DT_F32, 4><<<g, b, 0, st>>>(k);
+        else if (dtype == BS_BF16) bwd_rows2_kernel<DT_BF16, 4><<<g, b, 0, st>>>(k);
+        else if (dtype == BS_F16) bwd_rows2_kernel<DT_F16, 4><<<g, b, 0, st>>>(k);
+        else return BS_ERR_UNSUPPORTED;
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            set_error(e);
+            return BS_ERR_HIP;
+        }
+        return BS_OK;
     }
     if (k.wave_rows) {
         const PoolK &p = k.pool;

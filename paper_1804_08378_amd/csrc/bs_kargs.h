@@ -247,6 +247,7 @@ struct NhwcTile2K {
 // operation (pool.kind == 0: none).  Dense tensors only, row-major (NCHW) or channels-last.
 constexpr int K_BWD_EW = 16;
 constexpr int K_BWD_MAXROWS_RC = 8;  // window rows per chunk of the backward kernel that finds max-pooling picks itself
+constexpr int K_BWD_ROWS2_RC = 14;   // ... of the kernel that walks two pooling levels at once (a chunk revisits two window rows)
 struct BwdK {
     const void *a;        // the stage's input of the forward pass
     const void *g_out;    // gradient with respect to the stage's output
@@ -282,7 +283,9 @@ struct BwdK {
     // audit builds (-DBS_BWD_AUDIT): elements reachable from a / g_out / g_in, and where offsets beyond them are counted
     uint32_t audit_lim[3];
     uint32_t *audit;
-    int32_t wave_rows;
+    int32_t wave_rows;    // 2: two stages in one kernel -- `pool` (average 3 x 3 / 1 / 1) behind ew[0 .. n_ew), then `pool2` (max
+                          // 3 x 3 / 2 / 1) with ew[n_ew .. n_ew + n_post) behind it; H x W: the input plane, Ho x Wo: the max pooling's output
+    PoolK pool2;
     int32_t n_post;       // wave_rows, max pooling: element-wise operations (no Add) that follow the pooling, ew[n_ew .. n_ew + n_post):
                           // g_out is the gradient with respect to their output
     int32_t cbs, spw, chunks, rc;

@@ -193,10 +193,17 @@ def test_backward_stages_and_workspace():
     # pool, then element-wise operations: two stages; the second one's input and input gradient
     stages, ws = _backward_plan([bn(0), wl.relu(), wl.avgpool(2, 2), bn(1), wl.relu()], shape)
     assert (stages, ws) == (2, 2 * al(n_out * 4))
-    # three stages (the halo stress stack): stage 1 = max pooling alone, stage 2 = BatchNorm, ReLU
+    # the halo stress stack is three stages: BatchNorm, ReLU, average pooling | max pooling | BatchNorm, ReLU.  The last one
+    # joins the max pooling's stage, and the kernel that walks both pooling levels takes the first two: one stage, no workspace
     n_in = 2 * 8 * 16 * 16
-    stages, ws = _backward_plan([bn(0), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1), bn(1), wl.relu()], shape)
-    assert stages == 2 and ws >= 2 * al(n_in * 4)   # BatchNorm, ReLU behind the max pooling join its stage
+    halo = [bn(0), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1), bn(1), wl.relu()]
+    assert _backward_plan(halo, shape) == (1, 0)
+    assert _backward_plan(halo, shape, "bf16") == (1, 0)
+    # ... not with an Add in front of the average pooling, or with anything between the two poolings: two stages
+    stages, ws = _backward_plan([bn(0), wl.add(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1), bn(1), wl.relu()], shape)
+    assert stages == 2 and ws >= 2 * al(n_in * 4)
+    stages, ws = _backward_plan([bn(0), wl.relu(), wl.avgpool(3, 1, 1), wl.relu(), wl.maxpool(3, 2, 1), bn(1), wl.relu()], shape)
+    assert stages == 2 and ws >= 2 * al(n_in * 4)
     stages, ws = _backward_plan([bn(0), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1), bn(1), wl.relu()], shape, lane_exchange=-1)
     assert stages == 3 and ws >= 2 * al(n_in * 4) + al(n_out * 4) + 2 * al(n_out * 4)
     # capacity: 16 element-wise operations and 4 residual operands per stage

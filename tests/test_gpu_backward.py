@@ -161,6 +161,48 @@ def test_overlapping_max_windows_without_recorded_picks(shape, dtype):
     check(layers, shape, dtype, "own picks/pool_bn_relu", seed=9)
 
 
+def _two_level_stacks(c):
+    return {
+        "halo_stress": [wl.bn_params(c, 70), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1), wl.bn_params(c, 71), wl.relu()],
+        "in_range_count": [wl.bn_params(c, 72), wl.relu(), wl.avgpool(3, 1, 1, False), wl.maxpool(3, 2, 1), wl.bn_params(c, 73), wl.relu()],
+        "pools_only": [wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1)],
+        "leaky_clamp": [wl.bn_params(c, 74), wl.leaky_relu(0.2), wl.avgpool(3, 1, 1, False), wl.maxpool(3, 2, 1), wl.clamp(-0.3, 0.6),
+                        wl.bn_params(c, 75)],
+        "no_list_behind": [wl.clamp(-1.0, 1.5), wl.bn_params(c, 76), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1)],
+    }
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("shape", [(2, 3, 56, 56), (1, 2, 12, 16), (1, 2, 61, 24), (2, 2, 7, 8), (1, 1, 1, 8), (1, 1, 2, 8), (1, 2, 5, 256),
+                                   (2, 1, 70, 16), (1, 1, 90, 72)])
+def test_two_pooling_levels_in_one_backward_kernel(shape, dtype):
+    """Average pooling 3 x 3 / 1 / 1, then max pooling 3 x 3 / 2 / 1, with element-wise lists in front and behind: one
+    stage, one kernel, no workspace -- the plane between the poolings and its gradient stay in registers.  One, two
+    and more chunks of rows, odd and tiny heights, rows that fill a wave; both divisors of the average; ties in the
+    max windows.  Against the oracle and against the plan of separate stages."""
+    for name, layers in _two_level_stacks(shape[1]).items():
+        label = f"two levels/{name}"
+        x, res, dy = _inputs(layers, shape, 13, dtype)
+        x[:, :, ::3, 1::4] = 0.25   # equal values: ties between neighbouring averages
+        ref_x, _ = bw.backward_stack(layers, x, res, dy, dtype)
+        print(f"[backward] {label} shape={shape} dtype={dtype}", flush=True)
+        st = bs.Stack(layers, shape, dtype).plan().plan_backward()
+        assert bs.bs_stack_backward_num_stages(st.handle) == 1 and bs.bs_stack_backward_workspace_bytes(st.handle) == 0, label
+        st.close()
+        gx, _, _ = run_gpu(layers, x, res, dy, dtype)
+        hx, _, _ = run_gpu(layers, x, res, dy, dtype, lane_exchange=-1)
+        _close(gx, ref_x, dtype, label + " grad_x")
+        _close(hx, ref_x, dtype, label + " grad_x (separate stages)")
+    # an Add in front of the average, or an operation between the poolings: stages of their own
+    c = shape[1]
+    for layers in ([wl.add(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1)], [wl.avgpool(3, 1, 1), wl.relu(), wl.maxpool(3, 2, 1)],
+                   [wl.bn_params(c, 77), wl.avgpool(3, 1, 1), wl.maxpool(3, 1, 1)]):
+        st = bs.Stack(layers, shape, dtype).plan().plan_backward()
+        assert bs.bs_stack_backward_num_stages(st.handle) == 2
+        st.close()
+        check(layers, shape, dtype, "two levels/not fused", seed=17)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_disjoint_two_by_two_windows(dtype):
     c = 6
@@ -511,7 +553,7 @@ def test_repeated_calls_give_identical_bits():
     assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
-@pytest.mark.parametrize("name,dtype,layout", [("vgg_a", "f32", 0), ("vgg_c", "bf16", 0), ("resnet_tail", "f16", 0), ("halo_stress", "f32", 0),
+@pytest.mark.parametrize("name,dtype,layout", [("vgg_a", "f32", 0), ("vgg_c", "bf16", 0), ("resnet_tail", "f16", 0), ("halo_stress", "f32", 0), ("halo_stress", "bf16", 0),
                                                ("resnet_stem", "f16", 0), ("vgg_a", "f32", 1), ("resnet_stem", "f16", 1),
                                                ("resnet_tail", "bf16", 1), ("densenet_trans", "f32", 1)])
 def test_benchmark_sizes_on_sampled_images(name, dtype, layout):
