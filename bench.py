@@ -245,7 +245,7 @@ def launch_only(spec, launches):
     rocprofv3 counter and kernel-trace runs.  spec = NAME:DTYPE[:key=value,...]; NAME is a
     benchmark configuration or deepN (N blocks of MaxPool 3/1/1 -> BatchNorm -> ReLU on
     64 x 64 x 56 x 56); the keys are plan options (layout=1, lane_exchange=-1, force_variant=3,
-    max_steps_per_sequence=5 ...) and indices=1."""
+    max_steps_per_sequence=5 ...), indices=1 and backward=1 (the backward pass of the configuration)."""
     import torch
     from paper_1804_08378_amd import brainslug as bs
     from paper_1804_08378_amd import workloads as wl
@@ -255,7 +255,19 @@ def launch_only(spec, launches):
     opts = dict(kv.split("=") for kv in parts[2].split(",")) if len(parts) > 2 and parts[2] else {}
     opts = {k: int(v) for k, v in opts.items()}
     indices = bool(opts.pop("indices", 0))
-    if name.startswith("deep"):
+    backward = bool(opts.pop("backward", 0))
+    if backward:
+        layers, shape, _ = wl.build(name, 0, None, False)
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dt]
+        mf = torch.channels_last if opts.get("layout", 0) else torch.contiguous_format
+        rnd = lambda sh: torch.randn(sh, device="cuda").to(tdt).contiguous(memory_format=mf)
+        st = bs.Stack(layers, shape, dt).plan(**opts).plan_backward()
+        sets = [(rnd(shape), [rnd(sh) for sh in wl.residual_shapes(layers, shape)], rnd(wl.output_shape(layers, shape))) for _ in range(3)]
+        for i in range(launches):
+            x, res, dy = sets[i % 3]
+            st.backward(x, res, dy)
+        info = st.info()
+    elif name.startswith("deep"):
         c, n = 64, int(name[4:])
         layers = sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 100 + i), wl.relu()] for i in range(n)), [])
         tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dt]

@@ -65,7 +65,24 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // FLAT (row-major only): nfirst[j] cells of row j lie in channel c[j], the rest in the next channel
 // (a vector that straddles two planes).  Otherwise every cell of row j lies in channel c[j].
 // The list is k.ew[first .. first + count).
-template <int DT, int VEC, int R, bool CL, int NR, bool FLAT>
+// CODE >= 0: the kinds of the list's operations are known at compile time (one base-K_EW_BASE digit per operation, the first in
+// the lowest digit; `count` is ignored) and the loop over the list unrolls into straight code; their arguments still come from k.ew.
+constexpr int ew_code_len(int code)
+{
+    int n = 0;
+    while (code > 0) {
+        ++n;
+        code /= K_EW_BASE;
+    }
+    return n;
+}
+constexpr int ew_code_kind(int code, int q)
+{
+    for (int i = 0; i < q; ++i) code /= K_EW_BASE;
+    return code % K_EW_BASE;
+}
+
+template <int DT, int VEC, int R, bool CL, int NR, bool FLAT, int CODE = -1>
 BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC],
                              float (&t)[R][VEC], float (&r)[NR ? NR : 1][R][VEC], const uint32_t (&nfirst)[R], int32_t first,
                              int32_t count)
@@ -79,11 +96,9 @@ BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_
             for (int n = 0; n < NR; ++n) r[n][j][e] = 0.0f;
         }
     int32_t adds = 0;
-#pragma clang loop unroll(disable)
-    for (int32_t q = first; q < first + count; ++q) {
-        const int32_t kind = k.ew[q].kind, arg = k.ew[q].arg;
+    auto one = [&](const int32_t kind, const int32_t arg) {
         if (kind == OP_ADD) {
-            if constexpr (NR == 0) continue;  // instances for stages without Add (chosen at launch): nothing to read
+            if constexpr (NR == 0) return;  // instances for stages without Add (chosen at launch): nothing to read
             Raw<DT, VEC> raw[R];
 #pragma unroll
             for (int j = 0; j < R; ++j) raw[j] = load_raw<DT, VEC, true>(k.res[adds], off[j]);
@@ -104,7 +119,7 @@ BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_
                         for (int e = 0; e < VEC; ++e) r[n][j][e] = 1.0f;
                 }
             ++adds;
-            continue;
+            return;
         }
         float f[R][VEC];  // d(output) / d(input) of this operation at x
         if (kind == OP_BN) {
@@ -192,6 +207,13 @@ BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_
 #pragma unroll
                 for (int n = 0; n < NR; ++n) r[n][j][e] *= f[j][e];
             }
+    };
+    if constexpr (CODE >= 0) {
+#pragma unroll
+        for (int q = 0; q < ew_code_len(CODE); ++q) one(ew_code_kind(CODE, q), k.ew[first + q].arg);
+    } else {
+#pragma clang loop unroll(disable)
+        for (int32_t q = first; q < first + count; ++q) one(k.ew[q].kind, k.ew[q].arg);
     }
     return adds;
 }
@@ -726,17 +748,18 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
 //      gradients by the trailing list's derivative at the maxima and adds them to the picked cells
 //      (sums per a row; a pick in the left neighbour's column travels there by a lane shift),
 //   4. a rows 2 oh - 1 and 2 oh can get nothing more: their gradients, times the reciprocal of the
-//      average's divisor, become rows of `w` (with the neighbours' edge columns),
-//   5. writes the input gradient of rows 2 oh - 2 and 2 oh - 1: the 3 x 3 sum of w around the cell,
-//      times T.
+//      average's divisor, are summed over the three windows of the row that hold a cell (the
+//      neighbours' edge columns by lane shifts): rows of `hs`,
+//   5. writes the input gradient of rows 2 oh - 2 and 2 oh - 1: hs of the rows above, at and below, times T.
 // Rings: y rows 2 oh - 1 .. 2 oh + 2, T rows 2 oh - 2 .. 2 oh + 2, a rows 2 oh - 1 .. 2 oh + 1 and their
-// gradient sums, w rows 2 oh - 3 .. 2 oh.  A chunk of rc window rows writes input rows
+// gradient sums, hs rows 2 oh - 3 .. 2 oh.  A chunk of rc window rows writes input rows
 // [2 rc chunk, 2 rc (chunk + 1)) and visits window rows rc chunk - 1 .. rc (chunk + 1); every lane of
 // a wave runs the same number of iterations.  Sums have a fixed order: the same bits on every run.
 // The gradient between the two poolings stays in float32 registers (it is not rounded to the
 // storage type as it is between stages that run as separate kernels).
 // =============================================================================
-template <int DT, int VEC>
+// PRE, POST: the kinds of the leading and the trailing list as compile-time codes (ew_sweep_impl), or -1: read at run time.
+template <int DT, int VEC, int PRE, int POST>
 __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
 {
     constexpr int K = 3, S = 2, VO = VEC / S;
@@ -750,7 +773,7 @@ __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
     const int32_t oh_first = L.chunk * k.rc - 1;
     const int32_t n_iter = max(k.rc, (k.H - (k.chunks - 1) * k.rc * S + S - 1) / S) + 2;  // the same for every lane
 
-    float yf[4][YW], T[5][VEC], af[3][AW], gt[3][VEC], wf[4][YW];
+    float yf[4][YW], T[5][VEC], af[3][AW], gt[3][VEC], hs[4][VEC];
     const int32_t cs1[1] = {L.c};
 
     // rows [first, first + N) of the plane: leading element-wise list -> y with edge columns (padding +0: the
@@ -769,7 +792,8 @@ __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
         }
 #pragma unroll
         for (int j = 0; j < N; ++j) unpack<DT, VEC>(raw[j], xs[j]);
-        ew_sweep<DT, VEC, N, false, 0>(k, cs, offs, xs, ts, none);
+        const uint32_t whole[N] = {};
+        ew_sweep_impl<DT, VEC, N, false, 0, false, PRE>(k, cs, offs, xs, ts, none, whole, 0, k.n_ew);
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const bool ok = first + j >= 0 && first + j < k.H;
@@ -801,7 +825,7 @@ __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
 #pragma unroll
     for (int d = 0; d < 4; ++d)
 #pragma unroll
-        for (int e = 0; e < YW; ++e) wf[d][e] = 0.0f;
+        for (int e = 0; e < VEC; ++e) hs[d][e] = 0.0f;
     // y rows 2 oh - 2 .. 2 oh of the first window row -> a row 2 oh - 1; y rows 2 oh - 1, 2 oh stay
     take_rows(std::integral_constant<int, 3>{}, 0, 0, oh_first * S - 2);
     average_row(0, 0, oh_first * S - 1);
@@ -845,7 +869,7 @@ __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
             const uint32_t no_off[1] = {0}, all[1] = {VO};
 #pragma unroll
             for (int e = 0; e < VO; ++e) best[0][e] = row_ok ? best[0][e] : 0.0f;  // windows that do not exist: any finite value
-            ew_sweep_impl<DT, VO, 1, false, 0, false>(k, cs1, no_off, best, tp, none, all, k.n_ew, k.n_post);
+            ew_sweep_impl<DT, VO, 1, false, 0, false, POST>(k, cs1, no_off, best, tp, none, all, k.n_ew, k.n_post);
 #pragma unroll
             for (int e = 0; e < VO; ++e) g[e] *= tp[0][e];
         }
@@ -863,22 +887,25 @@ __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
                 }
             gt[dh][VEC - 1] += has_right ? from_right : 0.0f;
         }
-        // a rows hA and hA + 1 are complete: times the reciprocal of the average's divisor, with edge columns
+        // a rows hA and hA + 1 are complete: times the reciprocal of the average's divisor; per cell the sum over the
+        // three windows of that row that hold it (the neighbours' edge columns by lane shifts)
 #pragma unroll
         for (int d = 0; d < 2; ++d) {
             const int32_t row = min(max(hA + d, 0), k.H - 1);  // rows outside the plane hold zeros
-            float w[VEC];
+            float w[VEC], wf[YW];
 #pragma unroll
             for (int e = 0; e < VEC; ++e) w[e] = gt[d][e] * bwd_avg_inv(k.pool, k.H, k.W, row, col0 + e);
-            with_neighbours<VEC, 1, 1>(w, wf[2 + d], has_left, has_right, 0.0f);
+            with_neighbours<VEC, 1, 1>(w, wf, has_left, has_right, 0.0f);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) hs[2 + d][e] = (wf[e] + wf[e + 1]) + wf[e + 2];
         }
-        // input rows hA - 1 and hA: every average window that holds the cell, row-major, times the list's derivative
+        // input rows hA - 1 and hA: the window rows above, at and below the cell, times the list's derivative
 #pragma unroll
         for (int d = 0; d < 2; ++d) {
             const int32_t row = hA - 1 + d;
             float v[VEC];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) v[e] = xrows_window_sum<K, K, false, YW>(wf + d, e) * T[d][e];
+            for (int e = 0; e < VEC; ++e) v[e] = ((hs[d][e] + hs[d + 1][e]) + hs[d + 2][e]) * T[d][e];
             if (L.live && row >= r_lo && row < r_hi && k.g_in)
                 store_elems<DT, VEC>(k.g_in, audited(k, 2, 32, plane_off + (uint32_t)(row * k.W + col0) + L.img * k.gin_extra, VEC), v);
         }
@@ -887,8 +914,6 @@ __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
         for (int e = 0; e < YW; ++e) {
             yf[0][e] = yf[2][e];
             yf[1][e] = yf[3][e];
-            wf[0][e] = wf[2][e];
-            wf[1][e] = wf[3][e];
         }
 #pragma unroll
         for (int e = 0; e < AW; ++e) af[0][e] = af[2][e];
@@ -897,6 +922,8 @@ __global__ __launch_bounds__(256) void bwd_rows2_kernel(const BwdK k)
             T[0][e] = T[2][e];
             T[1][e] = T[3][e];
             T[2][e] = T[4][e];
+            hs[0][e] = hs[2][e];
+            hs[1][e] = hs[3][e];
             gt[0][e] = gt[2][e];
             gt[1][e] = 0.0f;
             gt[2][e] = 0.0f;
@@ -1160,10 +1187,25 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
             (int64_t)k.div_cbs.d != k.cbs || (int64_t)k.div_chunks.d != k.chunks || (int64_t)k.div_c.d != k.C ||
             (uint64_t)grid * 4 * k.spw < k.units)
             return BS_ERR_UNSUPPORTED;
-        if (dtype == BS_F32) bwd_rows2_kernel<DT_F32, 4><<<g, b, 0, st>>>(k);
-        else if (dtype == BS_BF16) bwd_rows2_kernel<DT_BF16, 4><<<g, b, 0, st>>>(k);
-        else if (dtype == BS_F16) bwd_rows2_kernel<DT_F16, 4><<<g, b, 0, st>>>(k);
+        // lists whose kinds are compiled in (BatchNorm, ReLU on both sides); any other goes through the run-time loops
+        auto code = [&](int32_t first, int32_t n) {
+            int32_t c = 0, digit = 1;
+            if (n > 6) return -1;
+            for (int32_t j = 0; j < n; ++j, digit *= K_EW_BASE) c += k.ew[first + j].kind * digit;
+            return c;
+        };
+        constexpr int BN_RELU = OP_BN + OP_RELU * K_EW_BASE;
+        const bool compiled = code(0, k.n_ew) == BN_RELU && code(k.n_ew, k.n_post) == BN_RELU;
+#define BS_LAUNCH_ROWS2(DT)                                                                     \
+    do {                                                                                        \
+        if (compiled) bwd_rows2_kernel<DT, 4, BN_RELU, BN_RELU><<<g, b, 0, st>>>(k);            \
+        else bwd_rows2_kernel<DT, 4, -1, -1><<<g, b, 0, st>>>(k);                               \
+    } while (0)
+        if (dtype == BS_F32) BS_LAUNCH_ROWS2(DT_F32);
+        else if (dtype == BS_BF16) BS_LAUNCH_ROWS2(DT_BF16);
+        else if (dtype == BS_F16) BS_LAUNCH_ROWS2(DT_F16);
         else return BS_ERR_UNSUPPORTED;
+#undef BS_LAUNCH_ROWS2
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             set_error(e);
