@@ -704,6 +704,9 @@ def main():
                            "us_hot_single_buffer": time_back_to_back(sb, "fused", args.steps, hot=True) * 1e3,
                            # work-items per launch of every sequence: what a kernel trace lists as grid size
                            "work_items": [q["grid"] * q["threads_per_group"] for q in sb.info["sequences"]]}
+                    # the same fraction from the back-to-back time (no event pair per launch: what a network's
+                    # stream of kernels sees); pct_peak above is the single-launch figure
+                    row["pct_peak_back_to_back"] = 100 * sb.bytes / (row["us_back_to_back"] * 1e-6) / 1e9 / HBM_PEAK_GBPS
                     rows.append(row)
                     log(f"{row['config']:<16}{dt:<6}{row['variant']:<13}{row['MB']:>8.1f}{row['us_mean']:>9.1f}"
                         f"{row['us_min']:>8.1f}{g:>8.0f}{row['pct_peak']:>7.1f}{row['img_s']:>10.0f}"
