@@ -166,13 +166,28 @@ constexpr int block_edge(int K, int S) { return K == 3 && S == 1 ? 2 : 1; }
 // vectors taken from the copies staged in LDS (`par`: the lane's vector of the list's first
 // BatchNorm scale; scale and shift of one operation, and operations, `stride` floats apart).
 //   off[u]  element offset of vector u inside its image, res_base: the image's first element (residual operands)
-template <int DT, int VEC, int U>
+// CODE >= 0: the kinds of the list's operations are known at compile time (one base-K_EW_BASE digit per operation, the first
+// in the lowest digit; n_ew is ignored) and the list unrolls into straight code; arguments still come from `ew`.
+constexpr int tile_code_len(int code)
+{
+    int n = 0;
+    while (code > 0) {
+        ++n;
+        code /= K_EW_BASE;
+    }
+    return n;
+}
+constexpr int tile_code_kind(int code, int q)
+{
+    for (int i = 0; i < q; ++i) code /= K_EW_BASE;
+    return code % K_EW_BASE;
+}
+
+template <int DT, int VEC, int U, int CODE = -1>
 BS_DEV void apply_ew_tile(float (&x)[U][VEC], const uint32_t (&off)[U], const EwOp *ew, int32_t n_ew, const float *par, uint32_t stride,
                           const float *__restrict__ params, const void *const *res, uint32_t res_base)
 {
-#pragma clang loop unroll(disable)
-    for (int32_t j = 0; j < n_ew; ++j) {
-        const int32_t kind = ew[j].kind, arg = ew[j].arg;
+    auto one = [&](const int32_t kind, const int32_t arg) {
         if (kind == OP_BN) {
             float sc[VEC], sh[VEC];
 #pragma unroll
@@ -216,6 +231,13 @@ BS_DEV void apply_ew_tile(float (&x)[U][VEC], const uint32_t (&off)[U], const Ew
                 for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(x[u][i] + r[i]);
             }
         }
+    };
+    if constexpr (CODE >= 0) {
+#pragma unroll
+        for (int j = 0; j < tile_code_len(CODE); ++j) one(tile_code_kind(CODE, j), ew[j].arg);
+    } else {
+#pragma clang loop unroll(disable)
+        for (int32_t j = 0; j < n_ew; ++j) one(ew[j].kind, ew[j].arg);
     }
 }
 
@@ -249,7 +271,9 @@ BS_DEV LaneBlock lane_block(uint32_t pl, bool lane_on, const FastDiv &div_bw, in
 //   (dh0, dw0)      plane position of its cell (0, 0); destination plane Hd x Wd, source plane Hs x Ws
 //   pad_next        what cells outside the destination plane hold (the next pool's padding)
 //   img             the image: residual operands and index outputs are dense tensors
-template <int DT, int VEC, int K, int S, bool TO_LDS>
+// CODE: the kinds of the level's element-wise list at compile time, or -1 (read at run time); KIND: the pooling
+// operation's kind, and no index output, or 0 (read at run time).
+template <int DT, int VEC, int K, int S, bool TO_LDS, int CODE = -1, int KIND = 0>
 BS_DEV void pool_level(const NhwcTile2K &k, const PoolK &p, const LaneBlock &lb, const uint4 *src, uint32_t src_w, uint4 *dst_lds,
                        int32_t dst_h, int32_t dst_w, uint32_t dst_pitch, int32_t dh0, int32_t dw0, int32_t Hs, int32_t Ws, int32_t Hd,
                        int32_t Wd, const EwOp *ew, int32_t n_ew, const float *par, uint32_t par_stride, float pad_next, uint32_t img,
@@ -258,8 +282,8 @@ BS_DEV void pool_level(const NhwcTile2K &k, const PoolK &p, const LaneBlock &lb,
     constexpr int B = block_edge(K, S), NB = B * B;
     constexpr uint32_t ES = DT == DT_F32 ? 4 : 2;
     const uint32_t cvb = (uint32_t)k.cvb;
-    const bool is_max = p.kind == OP_MAXPOOL;
-    const bool want_idx = !TO_LDS && is_max && k.idx != nullptr;  // the same for every lane
+    const bool is_max = KIND != 0 ? KIND == OP_MAXPOOL : p.kind == OP_MAXPOOL;
+    const bool want_idx = KIND == 0 && !TO_LDS && is_max && k.idx != nullptr;  // the same for every lane
     const int32_t r = lb.r, c = lb.c;
     const int32_t hd = dh0 + r, wd = dw0 + c;              // the block's first cell in the destination plane
     const int32_t hs = hd * S - p.ph, ws = wd * S - p.pw;  // first window's origin in the source plane
@@ -294,21 +318,20 @@ BS_DEV void pool_level(const NhwcTile2K &k, const PoolK &p, const LaneBlock &lb,
     // their pixels in the destination plane (clamped to it: safe addresses for the residual operands of cells outside)
     uint32_t pixel[NB], off[NB];
     const uint32_t img_off = img * (uint32_t)(Hd * Wd) * (uint32_t)k.C;  // the image's first element in a dense tensor
-    if (n_ew > 0 || !TO_LDS) {
+    const bool has_list = CODE >= 0 ? tile_code_len(CODE) > 0 : n_ew > 0;
+    if (has_list || !TO_LDS) {
 #pragma unroll
         for (int o = 0; o < NB; ++o) {
             pixel[o] = mad24((uint32_t)min(max(hd + o / B, 0), Hd - 1), (uint32_t)Wd, (uint32_t)min(max(wd + o % B, 0), Wd - 1));
             off[o] = mad24(pixel[o], (uint32_t)k.C, c0);
         }
     }
-    if (n_ew > 0) apply_ew_tile<DT, VEC, NB>(y, off, ew, n_ew, par, par_stride, k.params, k.res, img_off);
+    if (has_list) apply_ew_tile<DT, VEC, NB, CODE>(y, off, ew, n_ew, par, par_stride, k.params, k.res, img_off);
     if constexpr (TO_LDS) {
 #pragma unroll
         for (int o = 0; o < NB; ++o) {
-            if (!in[o]) {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) y[o][e] = pad_next;
-            }
+            for (int e = 0; e < VEC; ++e) y[o][e] = in[o] ? y[o][e] : pad_next;
             if (cell[o])
                 dst_lds[mad24(mad24((uint32_t)(r + o / B), dst_pitch, column_place((uint32_t)(c + o % B), dst_pitch)), cvb, cvl)] =
                     pack16<DT, VEC>(y[o]);
@@ -357,8 +380,25 @@ BS_DEV TilePlace tile_place(const NhwcTile2K &k, uint32_t t)
 // scratch memory; a second pooling step with stride 1 keeps a 4 x 4 block of cells per lane and gets one wave less.
 constexpr int tile_waves(int dt, int k2, int s2) { return (dt == DT_F32 ? 4 : 3) - (k2 == 3 && s2 == 1 ? 1 : 0); }
 
-template <int DT, int VEC, int K1, int S1, int K2, int S2>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(tile_waves(DT, K2, S2), tile_waves(DT, K2, S2)))) void nhwc_tile2_kernel(const NhwcTile2K k)
+// What an instance knows of the stack beyond its windows: the kinds of the three element-wise lists as codes (-1: read at run
+// time) and the kinds of the two pooling operations (0: read at run time; given, the instance writes no index output).
+// Measured on MI355X (stacked pooling of 128 x 128 x 56 x 56, microseconds, float32 / bfloat16 / binary16): nothing known
+// 89 / 108 / 106; lists known 77 / 98 / 94; lists and kinds known 94 / 87 / 83 -- with the kinds compiled in the scheduler
+// takes 155 registers for float32 (three waves per SIMD instead of four), while the 16-bit instances, at two to three
+// waves either way, gain from the shorter code.
+template <int PRE_, int MID_, int POST_, int KIND1_, int KIND2_>
+struct TileSig {
+    static constexpr int PRE = PRE_, MID = MID_, POST = POST_, KIND1 = KIND1_, KIND2 = KIND2_;
+    static constexpr int FEWER_WAVES = KIND1_ != 0 ? 1 : 0;  // instances that know the kinds may use one wave per SIMD less
+};
+using AnySig = TileSig<-1, -1, -1, 0, 0>;
+constexpr int K_CODE_BN_RELU = OP_BN + OP_RELU * K_EW_BASE;
+// BatchNorm, ReLU in front of the first pooling, nothing between the two, BatchNorm, ReLU behind the second (the stacked
+// pooling of Section 4.4 with its activations); the second also with average pooling first and max pooling second compiled in
+using BnReluSig = TileSig<K_CODE_BN_RELU, 0, K_CODE_BN_RELU, 0, 0>;
+using BnReluAvgMaxSig = TileSig<K_CODE_BN_RELU, 0, K_CODE_BN_RELU, OP_AVGSUM, OP_MAXPOOL>;
+template <int DT, int VEC, int K1, int S1, int K2, int S2, class SIG = AnySig>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(tile_waves(DT, K2, S2) - SIG::FEWER_WAVES, tile_waves(DT, K2, S2)))) void nhwc_tile2_kernel(const NhwcTile2K k)
 {
     extern __shared__ uint4 lds[];
     uint4 *lds0 = lds, *lds1 = lds + k.lds1_off;
@@ -394,7 +434,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(tile_waves(
     }
     const LaneBlock lb1 = lane_block<K1, S1>(pl, lane_on, k.div_bw1, k.r1h, (uint32_t)k.r0w, cvb, cvl);
     const LaneBlock lb2 = lane_block<K2, S2>(pl, lane_on, k.div_bw2, k.TH, (uint32_t)k.r1w, cvb, cvl);
-    const float pad0 = k.pool1.kind == OP_MAXPOOL ? -INFINITY : 0.0f, pad1 = k.pool2.kind == OP_MAXPOOL ? -INFINITY : 0.0f;
+    const float pad0 = (SIG::KIND1 != 0 ? SIG::KIND1 == OP_MAXPOOL : k.pool1.kind == OP_MAXPOOL) ? -INFINITY : 0.0f;
+    const float pad1 = (SIG::KIND2 != 0 ? SIG::KIND2 == OP_MAXPOOL : k.pool2.kind == OP_MAXPOOL) ? -INFINITY : 0.0f;
     const uint32_t pitch_b = ((uint32_t)k.C + k.in_xp) * ES;  // bytes from pixel to pixel of the input
     const uint32_t par_stride = cvb * VEC;                    // floats from one staged parameter vector set to the next
     const float *par_lane = par + cvl * VEC;
@@ -441,33 +482,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(tile_waves(
                 unpack<DT, VEC>(raw[u], x[u]);
                 off[u] = mad24(pixel[u], (uint32_t)k.C, c0);
             }
-            if (k.n_pre > 0)
-                apply_ew_tile<DT, VEC, U>(x, off, k.pre, k.n_pre, par_lane, par_stride, k.params, k.res,
-                                          tp.n * (uint32_t)(k.H * k.W) * (uint32_t)k.C);
+            if (SIG::PRE >= 0 ? tile_code_len(SIG::PRE) > 0 : k.n_pre > 0)
+                apply_ew_tile<DT, VEC, U, SIG::PRE>(x, off, k.pre, k.n_pre, par_lane, par_stride, k.params, k.res,
+                                                    tp.n * (uint32_t)(k.H * k.W) * (uint32_t)k.C);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (!(inside >> u & 1u)) {
+                const bool real = inside >> u & 1u;
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) x[u][e] = pad0;
-                }
+                for (int e = 0; e < VEC; ++e) x[u][e] = real ? x[u][e] : pad0;
                 if (cell_on[u]) lds0[cell_at[u]] = pack16<DT, VEC>(x[u]);
             }
         }
         __syncthreads();
-        // ---- request the next tile's cells; they arrive while the two pooling levels run
+        // ---- first pool, middle element-wise operations -> LDS
+        pool_level<DT, VEC, K1, S1, true, SIG::MID, SIG::KIND1>(k, k.pool1, lb1, lds0, (uint32_t)k.r0w, lds1, k.r1h, k.r1w, (uint32_t)k.r1w, tp.h10, tp.w10, k.H,
+                                          k.W, k.H1, k.W1, k.mid, k.n_mid, par_lane + 2u * (uint32_t)k.bn_base[1] * par_stride, par_stride,
+                                          pad1, tp.n, cvl, c0);
+        __syncthreads();
+        // ---- request the next tile's cells; they arrive while the second pooling level runs (requested before the
+        // first level: measured 4 % slower in float32, registers)
         const uint32_t t_next = t + 1;
         TilePlace tp_next = tp;
         if (t_next < t_end) {
             tp_next = tile_place<S1, S2>(k, t_next);
             request(tp_next);
         }
-        // ---- first pool, middle element-wise operations -> LDS
-        pool_level<DT, VEC, K1, S1, true>(k, k.pool1, lb1, lds0, (uint32_t)k.r0w, lds1, k.r1h, k.r1w, (uint32_t)k.r1w, tp.h10, tp.w10, k.H,
-                                          k.W, k.H1, k.W1, k.mid, k.n_mid, par_lane + 2u * (uint32_t)k.bn_base[1] * par_stride, par_stride,
-                                          pad1, tp.n, cvl, c0);
-        __syncthreads();
         // ---- second pool, trailing element-wise operations -> output
-        pool_level<DT, VEC, K2, S2, false>(k, k.pool2, lb2, lds1, (uint32_t)k.r1w, nullptr, min(k.TH, k.Ho - tp.oh0),
+        pool_level<DT, VEC, K2, S2, false, SIG::POST, SIG::KIND2>(k, k.pool2, lb2, lds1, (uint32_t)k.r1w, nullptr, min(k.TH, k.Ho - tp.oh0),
                                            min(k.TW, k.Wo - tp.ow0), 0u, tp.oh0, tp.ow0, k.H1, k.W1, k.Ho, k.Wo, k.post, k.n_post,
                                            par_lane + 2u * (uint32_t)k.bn_base[2] * par_stride, par_stride, 0.0f, tp.n, cvl, c0);
         if (t_next >= t_end) break;
@@ -581,6 +622,25 @@ bs_status launch_nhwc_tile2(const NhwcTile2K &k, int32_t dtype, int32_t vec, int
                      : dtype == BS_F16  ? instance_first<DT_F16, 8>(k.pool1, k.pool2)
                                         : nullptr;
     if (!fn) return BS_ERR_UNSUPPORTED;
+    // the instance that knows the whole stack, where there is one
+    {
+        auto code = [](const EwOp *ew, int32_t n) {
+            int32_t c = 0, digit = 1;
+            if (n > 6) return -1;
+            for (int32_t j = 0; j < n; ++j, digit *= K_EW_BASE) c += ew[j].kind * digit;
+            return c;
+        };
+        const PoolK &a = k.pool1, &b = k.pool2;
+        if (a.kh == 3 && a.sh == 1 && b.kh == 3 && b.sh == 2 && code(k.pre, k.n_pre) == K_CODE_BN_RELU && k.n_mid == 0 &&
+            code(k.post, k.n_post) == K_CODE_BN_RELU) {
+            const bool avg_max = a.kind == OP_AVGSUM && b.kind == OP_MAXPOOL && !k.idx;
+            if (dtype == BS_F32) fn = reinterpret_cast<const void *>(&nhwc_tile2_kernel<DT_F32, 4, 3, 1, 3, 2, BnReluSig>);
+            else if (dtype == BS_BF16 && avg_max) fn = reinterpret_cast<const void *>(&nhwc_tile2_kernel<DT_BF16, 8, 3, 1, 3, 2, BnReluAvgMaxSig>);
+            else if (dtype == BS_F16 && avg_max) fn = reinterpret_cast<const void *>(&nhwc_tile2_kernel<DT_F16, 8, 3, 1, 3, 2, BnReluAvgMaxSig>);
+            else if (dtype == BS_BF16) fn = reinterpret_cast<const void *>(&nhwc_tile2_kernel<DT_BF16, 8, 3, 1, 3, 2, BnReluSig>);
+            else fn = reinterpret_cast<const void *>(&nhwc_tile2_kernel<DT_F16, 8, 3, 1, 3, 2, BnReluSig>);
+        }
+    }
     // no more work-groups than the device holds at once: each walks its run of tiles from start to end
     int64_t groups = grid_n;
     {

@@ -828,6 +828,10 @@ def _tile_stacks(c):
                                             wl.maxpool(k2, s2, p2, True), wl.bn_params(c, 171), wl.relu()]
             stacks[f"max{a}_avg{b}"] = [wl.maxpool(k1, s1, p1), wl.bn_params(c, 172), wl.add(), wl.relu(),
                                         wl.avgpool(k2, s2, p2, False), wl.add()]
+    # the stacked pooling with its activations and no index output: the instances with the lists (and, 16-bit, the kinds) compiled in
+    stacks["halo_stress"] = [wl.bn_params(c, 168), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1), wl.bn_params(c, 169), wl.relu()]
+    stacks["halo_stress_in_range_count"] = [wl.bn_params(c, 168), wl.relu(), wl.avgpool(3, 1, 1, False), wl.maxpool(3, 2, 1),
+                                            wl.bn_params(c, 169), wl.relu()]
     stacks["max_max_lists_move"] = [wl.bn_params(c, 173), wl.relu(), wl.maxpool(3, 2, 1), wl.relu(), wl.bn_params(c, 174),
                                     wl.maxpool(3, 1, 1), wl.leaky_relu(0.2)]
     stacks["add_first"] = [wl.add(), wl.bn_params(c, 175), wl.maxpool(3, 1, 1), wl.clamp(-0.5, 0.75), wl.maxpool(2, 2, 0, True)]
