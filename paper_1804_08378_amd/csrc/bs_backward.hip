@@ -570,7 +570,8 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 // other rows belong to the neighbouring chunks.  Every lane of a wave runs the same number of
 // iterations whether or not its windows exist.
 // =============================================================================
-template <int DT, int VEC, int S, int NR, bool MAX>
+// PRE: the kinds of the stage's element-wise list as a compile-time code (ew_sweep_impl), or -1: read at run time.
+template <int DT, int VEC, int S, int NR, bool MAX, int PRE = -1>
 __global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
 {
     constexpr int K = 3, P = 1, VO = VEC / S, NL = P, NX = K - S - P, CW = NL + VEC + NX;
@@ -606,7 +607,8 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const BwdK k)
         }
 #pragma unroll
         for (int j = 0; j < N; ++j) unpack<DT, VEC>(raw[j], xs[j]);
-        adds = ew_sweep<DT, VEC, N, false, NR>(k, cs, offs, xs, ts, rs);
+        const uint32_t whole[N] = {};
+        adds = ew_sweep_impl<DT, VEC, N, false, NR, false, PRE>(k, cs, offs, xs, ts, rs, whole, 0, k.n_ew);
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const bool ok = first + j >= 0 && first + j < k.H;
@@ -1232,9 +1234,13 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
             (int64_t)(k.chunks - 1) * k.rc * p.sh >= k.H || (int64_t)k.div_cbs.d != k.cbs || (int64_t)k.div_chunks.d != k.chunks ||
             (int64_t)k.div_c.d != k.C || (uint64_t)grid * 4 * k.spw < k.units)
             return BS_ERR_UNSUPPORTED;
+        // BatchNorm, ReLU in front of a max pooling with stride 2 (the ResNet stem): the kinds of the list compiled in
+        constexpr int BN_RELU = OP_BN + OP_RELU * K_EW_BASE;
+        const bool bn_relu = k.n_ew == 2 && k.ew[0].kind == OP_BN && k.ew[1].kind == OP_RELU;
 #define BS_LAUNCH_MAXROWS(DT, V)                                                               \
     do {                                                                                       \
-        if (is_max && p.sh == 2 && n_add == 0) bwd_rows_kernel<DT, V, 2, 0, true><<<g, b, 0, st>>>(k);          \
+        if (is_max && p.sh == 2 && bn_relu && k.n_post == 0) bwd_rows_kernel<DT, V, 2, 0, true, BN_RELU><<<g, b, 0, st>>>(k); \
+        else if (is_max && p.sh == 2 && n_add == 0) bwd_rows_kernel<DT, V, 2, 0, true><<<g, b, 0, st>>>(k);     \
         else if (is_max && p.sh == 2) bwd_rows_kernel<DT, V, 2, K_MAX_RES, true><<<g, b, 0, st>>>(k);           \
         else if (is_max && n_add == 0) bwd_rows_kernel<DT, V, 1, 0, true><<<g, b, 0, st>>>(k);                  \
         else if (is_max) bwd_rows_kernel<DT, V, 1, K_MAX_RES, true><<<g, b, 0, st>>>(k);                        \
