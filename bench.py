@@ -240,6 +240,44 @@ def issue_rates(iterations=20000, clock_ghz=2.4):
     return rows
 
 
+def hbm_patterns(out_mb=(26, 103), launches=40):
+    """What the chip's memory system delivers for streaming access patterns with no arithmetic
+    (bs_probe_stream): pure reads, a copy, and four bytes read per byte written (the pattern of a
+    2 x 2 pooling step), at the output sizes of vgg_c and vgg_a, over rotating buffers (>= 1 GB
+    touched between two uses of a buffer).  Back-to-back launches between two events."""
+    import torch
+    from paper_1804_08378_amd import brainslug as bs
+
+    stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+    g = torch.Generator(device="cuda").manual_seed(0)
+    for mb in out_mb:
+        out_bytes = mb * 1000 * 1000 // 16 * 16
+        for rpw, read_only, label in ((4, True, "read only"), (1, False, "copy 1:1"), (2, False, "read 2 : write 1"), (4, False, "read 4 : write 1")):
+            in_bytes = out_bytes * rpw
+            moved = in_bytes + (0 if read_only else out_bytes)
+            sets = max(2, min(16, (1 << 30) // moved + 1))
+            ins = [torch.randint(0, 2 ** 31 - 1, (in_bytes // 4,), dtype=torch.int32, device="cuda", generator=g) for _ in range(sets)]
+            outs = [torch.empty(out_bytes // 4, dtype=torch.int32, device="cuda") for _ in range(sets)]
+            for i in range(3):
+                bs.bs_probe_stream(rpw, read_only, ins[i % sets].data_ptr(), in_bytes, outs[i % sets].data_ptr(), out_bytes, stream)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for i in range(launches):
+                bs.bs_probe_stream(rpw, read_only, ins[i % sets].data_ptr(), in_bytes, outs[i % sets].data_ptr(), out_bytes, stream)
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / launches
+            row = {"pattern": label, "MB_moved": moved / 1e6, "us_per_launch": us, "GBps": moved / (us * 1e-6) / 1e9,
+                   "pct_peak": 100 * moved / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+            rows.append(row)
+            log(f"hbm_pattern {label:<18}{row['MB_moved']:>8.1f} MB{us:>8.1f} us{row['GBps']:>8.0f} GB/s{row['pct_peak']:>6.1f} % of peak")
+            del ins, outs
+            torch.cuda.empty_cache()
+    return rows
+
+
 def launch_only(spec, launches):
     """`launches` launches of one configuration and nothing else (no timing): the leg for
     rocprofv3 counter and kernel-trace runs.  spec = NAME:DTYPE[:key=value,...]; NAME is a
@@ -538,6 +576,8 @@ def main():
                          "time = fixed cost + bytes / rate")
     ap.add_argument("--issue-rates", action="store_true",
                     help="also measure the device's instruction issue rates (bs_probe_issue_rate)")
+    ap.add_argument("--hbm-patterns", action="store_true",
+                    help="also measure what streaming access patterns without arithmetic reach (bs_probe_stream)")
     ap.add_argument("--launch", nargs=2, metavar=("SPEC", "N"),
                     help="only launch one configuration N times (for rocprofv3): SPEC = NAME:DTYPE[:key=value,...]")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
@@ -654,6 +694,10 @@ def main():
         out["all_configs"] = all_configs_summary()
     if args.issue_rates:
         out["issue_rates"] = issue_rates()
+    if args.hbm_patterns:
+        stacks = None
+        torch.cuda.empty_cache()
+        out["hbm_patterns"] = hbm_patterns()
     if args.batch_fit:
         stacks = None
         torch.cuda.empty_cache()

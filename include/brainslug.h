@@ -493,6 +493,21 @@ typedef enum bs_probe_kind {
 BS_API bs_status bs_probe_issue_rate(int32_t kind, int32_t waves_per_simd, int32_t iterations, float *sink,
                                      uint64_t sink_floats, void *stream);
 
+/*
+ * Measurement aid (the roofline the streaming kernels are priced against): enqueue a kernel with no
+ * arithmetic in which every lane reads `reads_per_write` (1, 2 or 4) 128-bit vectors from `in` --
+ * that many streams, each contiguous across the lanes, non-temporal loads as in the streaming
+ * kernels -- and writes one vector to `out`: 4 = the four-bytes-in-per-byte-out pattern of a 2 x 2
+ * pooling step, 1 = a copy.  read_only != 0: the same loads, nothing written (out is still needed
+ * and must hold out_bytes).  The caller times the launch; bytes moved = out_bytes * reads_per_write
+ * (+ out_bytes unless read_only).
+ *   in, out      device, 16-byte aligned, not overlapping; in_bytes >= out_bytes * reads_per_write
+ *   out_bytes    a multiple of 16, at most 2^31 - 1 vectors
+ * Errors: BS_ERR_NULL, BS_ERR_PARAM, BS_ERR_WORKSPACE (in too small), BS_ERR_ALIGN, BS_ERR_HIP.
+ */
+BS_API bs_status bs_probe_stream(int32_t reads_per_write, int32_t read_only, const void *in, uint64_t in_bytes, void *out,
+                                 uint64_t out_bytes, void *stream);
+
 /* Static, never NULL. */
 BS_API const char *bs_status_string(bs_status status);
 BS_API const char *bs_version(void);

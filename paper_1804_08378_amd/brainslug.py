@@ -114,6 +114,7 @@ _SIGNATURES = {
                                             C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.POINTER(C.c_void_p), C.c_void_p,
                                             C.c_uint64, C.c_void_p]),
     "bs_probe_issue_rate": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "bs_probe_stream": (C.c_int, [C.c_int32, C.c_int32, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]),
     "bs_stack_jit_check": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_int32)]),
     "bs_jit_log": (C.c_char_p, []),
     "bs_status_string": (C.c_char_p, [C.c_int]),
@@ -358,6 +359,12 @@ def bs_static_workspace_capacity() -> int:
 
 PROBE_KINDS = {"add": 0, "fma": 1, "max3": 2, "select_vcc": 3, "select_sgpr": 4, "lane_shift": 5, "add_scalar": 6,
                "add_branch": 7, "dependent_add": 8}
+
+
+def bs_probe_stream(reads_per_write: int, read_only: bool, in_ptr: int, in_bytes: int, out_ptr: int, out_bytes: int, stream) -> None:
+    """Enqueue the streaming probe (no arithmetic); *_ptr are integer device addresses."""
+    _check(load().bs_probe_stream(int(reads_per_write), int(bool(read_only)), C.c_void_p(in_ptr or None), int(in_bytes),
+                                  C.c_void_p(out_ptr or None), int(out_bytes), C.c_void_p(stream or None)), "bs_probe_stream")
 
 
 def bs_probe_issue_rate(kind: int, waves_per_simd: int, iterations: int, sink_ptr: int, sink_floats: int, stream) -> None:

@@ -44,10 +44,59 @@ BS_PROBE(add_salu, "", I_ADD_SALU, "", "s20", "scc")
 BS_PROBE(add_branch, "s_cmp_lg_u32 0, 0\n", I_ADD_BRANCH, "1:\n", "scc")
 BS_PROBE(chain, "", I_CHAIN, "", "memory")
 
+// Streaming probe: what HBM delivers for an access pattern with no arithmetic at all.  Every lane
+// reads R consecutive-per-wave 128-bit vectors (non-temporal, as the streaming kernels do) and
+// writes one (R = 4: four bytes read per byte written, the pattern of a 2 x 2 pooling step;
+// R = 1: a copy).  READ_ONLY: the vectors are folded together and stored only if the fold hits
+// a value random data never produces, so the loads stay but nothing is written.
+template <int R, bool READ_ONLY>
+__global__ __launch_bounds__(256) void probe_stream_kernel(const uint4 *in, uint4 *out, uint32_t n_out)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= n_out) return;
+    // lane i reads vectors r * n_out + i: R streams, each contiguous across the lanes
+    u4 acc = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc ^= __builtin_nontemporal_load(reinterpret_cast<const u4 *>(in) + (size_t)r * n_out + i);
+    if (READ_ONLY && (acc.x != 0x7fc12345u || acc.y != 0x7fc12345u)) return;
+    __builtin_nontemporal_store(acc, reinterpret_cast<u4 *>(out) + i);
+}
+
 }  // namespace
 }  // namespace bs
 
 using namespace bs;
+
+extern "C" bs_status bs_probe_stream(int32_t reads_per_write, int32_t read_only, const void *in, uint64_t in_bytes, void *out,
+                                     uint64_t out_bytes, void *stream)
+{
+    if (!in || !out) return BS_ERR_NULL;
+    if (reads_per_write != 1 && reads_per_write != 2 && reads_per_write != 4) return BS_ERR_PARAM;
+    if (out_bytes == 0 || out_bytes % 16 != 0 || out_bytes / 16 > 0x7fffffffull) return BS_ERR_PARAM;
+    if (in_bytes < out_bytes * (uint64_t)reads_per_write) return BS_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15u) return BS_ERR_ALIGN;
+    const uint32_t n_out = (uint32_t)(out_bytes / 16);
+    const dim3 g((n_out + 255u) / 256u), b(256);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint4 *src = static_cast<const uint4 *>(in);
+    uint4 *dst = static_cast<uint4 *>(out);
+    if (read_only) {
+        if (reads_per_write == 1) probe_stream_kernel<1, true><<<g, b, 0, st>>>(src, dst, n_out);
+        else if (reads_per_write == 2) probe_stream_kernel<2, true><<<g, b, 0, st>>>(src, dst, n_out);
+        else probe_stream_kernel<4, true><<<g, b, 0, st>>>(src, dst, n_out);
+    } else {
+        if (reads_per_write == 1) probe_stream_kernel<1, false><<<g, b, 0, st>>>(src, dst, n_out);
+        else if (reads_per_write == 2) probe_stream_kernel<2, false><<<g, b, 0, st>>>(src, dst, n_out);
+        else probe_stream_kernel<4, false><<<g, b, 0, st>>>(src, dst, n_out);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_hip_error((int32_t)e);
+        return BS_ERR_HIP;
+    }
+    return BS_OK;
+}
 
 extern "C" bs_status bs_probe_issue_rate(int32_t kind, int32_t waves_per_simd, int32_t iterations, float *sink,
                                          uint64_t sink_floats, void *stream)

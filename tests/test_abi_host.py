@@ -343,6 +343,23 @@ def test_buffer_checks_against_brute_force_byte_sets():
         bs.bs_stack_destroy(hd)
 
 
+def test_probe_arguments_are_checked_before_anything_is_launched():
+    """The measurement aids refuse bad arguments on the host (fake addresses, no device needed)."""
+    def status(call):
+        with pytest.raises(bs.BrainSlugError) as e:
+            call()
+        return bs.STATUS_NAMES[e.value.status]
+
+    a, b = 1 << 20, 2 << 20
+    assert status(lambda: bs.bs_probe_stream(4, False, 0, 64, b, 16, 0)) == "BS_ERR_NULL"
+    assert status(lambda: bs.bs_probe_stream(3, False, a, 64, b, 16, 0)) == "BS_ERR_PARAM"      # 1, 2 or 4 reads per write
+    assert status(lambda: bs.bs_probe_stream(4, False, a, 64, b, 24, 0)) == "BS_ERR_PARAM"      # whole 128-bit vectors
+    assert status(lambda: bs.bs_probe_stream(4, False, a, 63, b, 16, 0)) == "BS_ERR_WORKSPACE"  # the input holds 4 x the output
+    assert status(lambda: bs.bs_probe_stream(1, True, a + 8, 64, b, 16, 0)) == "BS_ERR_ALIGN"
+    assert status(lambda: bs.bs_probe_issue_rate(0, 1, 10, 0, 1 << 20, 0)) == "BS_ERR_NULL"
+    assert status(lambda: bs.bs_probe_issue_rate(0, 9, 10, a, 1 << 20, 0)) == "BS_ERR_PARAM"
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(bs, "_lib", None)
     monkeypatch.setattr(bs, "LIB_PATH", "/nonexistent/libbrainslug_hip.so")

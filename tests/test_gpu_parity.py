@@ -1092,3 +1092,26 @@ def test_one_planned_handle_runs_on_two_streams_at_once():
             assert np.array_equal(o.cpu().numpy().view(np.uint32), ref.view(np.uint32)), (i, r)
             assert np.array_equal(idx[0].cpu().numpy(), ref_idx[0]), (i, r)
     st.close()
+
+
+def test_streaming_probe_moves_what_it_says():
+    """bs_probe_stream (the no-arithmetic kernel the roofline notes are priced against): the copy
+    pattern copies, R reads per write give the exclusive-or of the R streams, a read-only launch
+    writes nothing."""
+    n = 3 * 1024 * 256 + 40  # vectors: whole work-groups and a ragged tail
+    g = torch.Generator(device="cuda").manual_seed(3)
+    stream = torch.cuda.current_stream().cuda_stream
+    for r in (1, 2, 4):
+        src = torch.randint(-2 ** 31, 2 ** 31 - 1, (r, n, 4), dtype=torch.int32, device="cuda", generator=g)
+        dst = torch.full((n, 4), 77, dtype=torch.int32, device="cuda")
+        bs.bs_probe_stream(r, False, src.data_ptr(), src.numel() * 4, dst.data_ptr(), dst.numel() * 4, stream)
+        torch.cuda.synchronize()
+        want = src[0].clone()
+        for j in range(1, r):
+            want ^= src[j]
+        assert torch.equal(dst, want)
+        dst.fill_(77)
+        bs.bs_probe_stream(r, True, src.data_ptr(), src.numel() * 4, dst.data_ptr(), dst.numel() * 4, stream)
+        torch.cuda.synchronize()
+        assert bool((dst == 77).all())
+
