@@ -776,8 +776,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BS_ROWS2_WA
     const bool has_left = L.j > 0, has_right = L.j + 1 < k.cbs;
     const uint32_t plane_off = L.plane * (uint32_t)(k.H * k.W), oplane = L.plane * (uint32_t)(k.Ho * k.Wo);
     const int32_t r_lo = L.chunk * k.rc * S, r_hi = L.chunk + 1 == k.chunks ? k.H : min(r_lo + k.rc * S, k.H);
-    const int32_t oh_first = L.chunk * k.rc - 1;
-    const int32_t n_iter = max(k.rc, (k.H - (k.chunks - 1) * k.rc * S + S - 1) / S) + 2;  // the same for every lane
+    // a chunk starts one window row early (that row's windows reach into the chunk's first row) -- not when the chunk is
+    // the whole plane: there is no window row above the first
+    const int32_t lead = k.chunks > 1 ? 1 : 0;
+    const int32_t oh_first = L.chunk * k.rc - lead;
+    const int32_t n_iter = max(k.rc, (k.H - (k.chunks - 1) * k.rc * S + S - 1) / S) + 1 + lead;  // the same for every lane
 
     float yf[4][YW], T[5][VEC], af[3][AW], gt[3][VEC], hs[4][VEC];
     const int32_t cs1[1] = {L.c};
