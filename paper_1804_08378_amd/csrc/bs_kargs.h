@@ -246,7 +246,12 @@ struct NhwcTile2K {
 // Backward pass of one stage: element-wise operations followed by at most one pooling
 // operation (pool.kind == 0: none).  Dense tensors only, row-major (NCHW) or channels-last.
 constexpr int K_BWD_EW = 16;
-constexpr int K_BWD_MAXROWS_RC = 8;  // window rows per chunk of the backward kernel that finds max-pooling picks itself
+#if !defined(BS_MAXROWS_RC)
+#define BS_MAXROWS_RC 8
+#endif
+// Window rows per chunk of the backward kernel that finds max-pooling picks itself.  Measured on MI355X (ResNet stem, 56 window
+// rows, float32 / bfloat16): 8 -> 94 / 73 us, 14 -> 99 / 73, 28 -> 95 / 76, 56 -> 101 / 107.
+constexpr int K_BWD_MAXROWS_RC = BS_MAXROWS_RC;
 #if !defined(BS_ROWS2_RC)
 #define BS_ROWS2_RC 28
 #endif
