@@ -51,6 +51,7 @@ struct Sequence {
     PoolDirectK direct{};
     PoolRowsK rows{};
     PoolRows2K rows2{};
+    RowsChainK chain{};
     LdsSeqK lds{};
     NhwcK nhwc{};
     NhwcTile2K nhwc2{};
@@ -197,6 +198,9 @@ bool xrows_launchable(const PoolRowsK &k, int32_t dtype, int64_t grid, int32_t t
 bool xrows2_launchable(const PoolRows2K &k, int32_t dtype, int64_t grid, int32_t threads);
 bs_status launch_xrows(const PoolRowsK &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
 bs_status launch_xrows2(const PoolRows2K &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
+// the chain kernel: is there an instance for this pooling shape, list and depth / launch it
+bool xrows_chain_supported(const RowsChainK &k, int32_t dtype);
+bs_status launch_xrows_chain(const RowsChainK &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
 bool lds_fast_path(const LdsSeqK &k);
 bool lds_precompiled(const LdsSeqK &k, int32_t dtype);

@@ -194,6 +194,25 @@ struct PoolRows2K {
     uint32_t units;   // segments = planes * chunks
 };
 
+// A chain of identical pooling steps that keep the plane's size (window k, stride 1, padding (k - 1) / 2), each followed
+// by the same kinds of element-wise operations: the stacked blocks of Section 5.1 in the register kernel whose lanes
+// exchange edge columns.  A lane walks down a chunk of rc output rows and the n_levels * (kh - 1) / 2 rows above and below it.
+constexpr int K_CHAIN_MAX = 8;
+struct RowsChainK {
+    const void *in;
+    void *out;
+    const float *params;
+    uint32_t in_extra, out_extra;  // elements to skip per image beyond a dense one: batch stride - C*H*W (0 = dense)
+    int32_t n_levels;              // pooling steps, 3 .. K_CHAIN_MAX
+    int32_t n_ew;                  // element-wise operations behind each of them
+    EwOp ew[K_CHAIN_MAX][K_MAX_EW];
+    PoolK pool;
+    int32_t C, H, W;
+    int32_t rc, chunks, cbs, spw;  // as in PoolRows2K
+    uint32_t units;
+    FastDiv div_cbs, div_chunks, div_c;
+};
+
 // Channels-last (N, H, W, C in memory) sequences: element-wise only (pool.kind == 0, the list
 // in `pre`) or one pooling operation with element-wise operations before and after it.
 struct NhwcK {

@@ -660,6 +660,14 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         if (ls != BS_OK) return ls;
         break;
     }
+    case BS_VARIANT_ROWS_CHAIN: {
+        RowsChainK k = q.chain;
+        k.in = in; k.out = out; k.params = s->dev_params;
+        k.in_extra = in_extra; k.out_extra = out_extra;
+        const bs_status ls = launch_xrows_chain(k, dtype, q.grid, q.threads, stream);
+        if (ls != BS_OK) return ls;
+        break;
+    }
     case BS_VARIANT_LDS_TILE: {
         LdsSeqK k = q.lds;
         k.in = in; k.out = out; k.params = s->dev_params;

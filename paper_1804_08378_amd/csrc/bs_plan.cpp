@@ -335,6 +335,7 @@ static bool direct_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops
 // smallest useful tile, including the overlap that padding / k > s adds at every level.
 static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill);
 static bool plane_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops);
+static bool chain_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill);
 
 static uint64_t seq_min_lds(const bs_stack *s, int32_t first_op, int32_t n_ops, int32_t threads)
 {
@@ -342,6 +343,7 @@ static uint64_t seq_min_lds(const bs_stack *s, int32_t first_op, int32_t n_ops, 
     if (direct_applicable(s, first_op, n_ops) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
     if (rows_applicable(s, first_op, n_ops, nullptr) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
     if (plane_applicable(s, first_op, n_ops) && s->opts.force_variant != BS_VARIANT_LDS_TILE) return 0;
+    if (chain_applicable(s, first_op, n_ops, nullptr)) return 0;
     const Op &last = s->ops[first_op + n_ops - 1];
     int32_t th, tw;
     min_tile(last.out_h, last.out_w, threads, th, tw);
@@ -898,6 +900,94 @@ static void plan_exchange(Sequence &q, K &k, int64_t planes, int32_t rc, int32_t
     q.grid = ((int64_t)k.units + per_group - 1) / per_group;
 }
 
+// Three and more identical max-pooling steps that keep the plane's size (odd window, stride 1, padding (k - 1) / 2,
+// no index output), each followed by element-wise operations of the same kinds (no Add), nothing in front of the
+// first: the blocks of Section 5.1.  The chain kernel exists for the shapes and lists compiled into the library, on
+// planes whose rows fit one wave; anything else takes the LDS tiles.
+static bool chain_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill)
+{
+    if (s->opts.layout == BS_LAYOUT_NHWC || s->opts.force_variant == BS_VARIANT_LDS_TILE) return false;
+    Sequence tmp;
+    Sequence &q = fill ? *fill : tmp;
+    RowsChainK k{};
+    int32_t level = -1, n_here = 0;
+    for (int32_t i = first_op; i < first_op + n_ops; ++i) {
+        const Op &op = s->ops[i];
+        if (!op_is_elementwise(op.kind)) {
+            if (op.kind != OP_MAXPOOL || op.idx_slot >= 0 || op.sh != 1 || op.sw != 1 || op.kh != 2 * op.ph + 1 ||
+                op.kw != 2 * op.pw + 1 || op.out_h != op.in_h || op.out_w != op.in_w)
+                return false;
+            if (level >= 0 && n_here != k.n_ew) return false;  // every level has the same list length
+            if (++level >= K_CHAIN_MAX) return false;
+            const PoolK p = make_pool(op, nullptr, q);
+            if (level == 0) {
+                k.pool = p;
+                k.H = op.in_h;
+                k.W = op.in_w;
+            } else if (p.kh != k.pool.kh || p.kw != k.pool.kw || p.ph != k.pool.ph || p.pw != k.pool.pw) {
+                return false;
+            }
+            n_here = 0;
+        } else if (op.kind != OP_AVGNORM) {
+            if (level < 0 || op.kind == OP_ADD || n_here >= K_MAX_EW) return false;
+            fill_ew(s, op, q, k.ew[level][n_here]);
+            if (level > 0 && k.ew[level][n_here].kind != k.ew[0][n_here].kind) return false;
+            ++n_here;
+            if (level == 0) k.n_ew = n_here;
+        }
+    }
+    if (level < 2 || n_here != k.n_ew) return false;
+    k.n_levels = level + 1;
+    const int32_t vec = xrows_vec(s->dtype);
+    if (!exchange_fits(s, k.W, vec) || !xrows_chain_supported(k, s->dtype)) return false;
+    k.cbs = k.W / vec;
+    k.spw = 64 / k.cbs;
+    if (fill) fill->chain = k;
+    return true;
+}
+
+static void plan_chain(const bs_stack *s, Sequence &q, const bs_plan_options &o)
+{
+    q.variant = BS_VARIANT_ROWS_CHAIN;
+    q.n_idx = 0;
+    chain_applicable(s, q.first_op, q.n_ops, &q);
+    RowsChainK &k = q.chain;
+    q.vec = xrows_vec(s->dtype);
+    k.C = (int32_t)q.in_shape[1];
+    const int64_t planes = q.in_shape[0] * q.in_shape[1];
+    // Output rows per lane.  A chunk also computes the n_levels * ph rows above and below it at the first level (one
+    // fewer per level after that): longer chunks recompute less, shorter ones give more waves.  Half the plane
+    // (measured on 56 x 56 planes, 5 levels, float32: 7 / 14 / 19 / 28 / 56 rows -> 8.1 / 6.5 / 6.4 / 6.3 / 6.7 us per
+    // block), and at least as many rows as the chunk recomputes.
+    const int32_t halo = 2 * k.n_levels * k.pool.ph;
+    int32_t rc = std::max(halo, (k.H + 1) / 2);
+    if (o.tile_rows > 0) rc = o.tile_rows;
+    rc = std::max(1, std::min(rc, k.H));
+    k.chunks = (k.H + rc - 1) / rc;
+    k.rc = (k.H + k.chunks - 1) / k.chunks;
+    k.chunks = (k.H + k.rc - 1) / k.rc;
+    k.units = (uint32_t)(planes * k.chunks);
+    k.div_cbs = make_fastdiv((uint32_t)k.cbs);
+    k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+    k.div_c = make_fastdiv((uint32_t)k.C);
+    q.threads = 256;
+    const int64_t per_group = (int64_t)k.spw * (q.threads / 64);
+    q.grid = ((int64_t)k.units + per_group - 1) / per_group;
+    q.lds_bytes = 0;
+    q.tile_rows = k.rc;
+    q.tile_cols = k.W;
+    q.planes_per_group = 0;
+    q.n_levels = k.n_levels;
+    q.halo_rows = halo;
+    q.halo_cols = 0;
+    double rows_loaded = 0;
+    for (int32_t ch = 0; ch < k.chunks; ++ch) {
+        const int32_t a = ch * k.rc, b = std::min(k.H, a + k.rc);
+        rows_loaded += std::min(k.H, b + halo / 2) - std::max(0, a - halo / 2);
+    }
+    q.redundancy = rows_loaded / (double)k.H;
+}
+
 static void plan_rows2(const bs_stack *s, Sequence &q, const bs_plan_options &o)
 {
     PoolRows2K &k = q.rows2;
@@ -1002,7 +1092,7 @@ static bool seq_is_fast(const bs_stack *s, int32_t first_op, int32_t n_ops)
 {
     if (count_pools(s, first_op, n_ops) == 0) return true;
     if (direct_applicable(s, first_op, n_ops) || rows_applicable(s, first_op, n_ops, nullptr) ||
-        plane_applicable(s, first_op, n_ops))
+        plane_applicable(s, first_op, n_ops) || chain_applicable(s, first_op, n_ops, nullptr))
         return true;
     if (!seq_capacity_ok(s, first_op, n_ops, false)) return false;
     if (jit_allowed(s)) return true;  // any signature gets its own build
@@ -1365,11 +1455,26 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
         // memory, once a few steps are fused -- measured on MI355X, four to five steps per
         // sequence are fastest.  Cap sequences at K_AUTO_STEPS steps, then even out their
         // lengths (8 steps run as 4 + 4 rather than 5 + 3).
-        bs_status fs = fill(K_AUTO_STEPS, drafts);
+        // Chains of identical blocks that the register kernel takes are the exception: it has no LDS
+        // traffic and measured fastest with as many levels as it is compiled for (64 x 64 x 56 x 56,
+        // float32: 9.0 / 7.1 / 6.3 / 6.0 / 5.6 us per block with 3 / 4 / 5 / 6 / 8 levels).
+        int32_t cap = K_AUTO_STEPS;
+        {
+            std::vector<SeqDraft> longer;
+            bool all_chains = fill(K_CHAIN_MAX, longer) == BS_OK && !longer.empty();
+            for (const SeqDraft &d : longer) {
+                int32_t fo, no;
+                range_ops(d, fo, no);
+                all_chains = all_chains && (d.n_steps < 3 || chain_applicable(s, fo, no, nullptr));
+                all_chains = all_chains && (d.n_steps >= 3 || longer.size() > 1);
+            }
+            if (all_chains) cap = K_CHAIN_MAX;
+        }
+        bs_status fs = fill(cap, drafts);
         if (fs != BS_OK) return fs;
         const int32_t n_seq = (int32_t)drafts.size(), n_steps = (int32_t)s->steps.size();
         const int32_t even = n_seq > 0 ? (n_steps + n_seq - 1) / n_seq : 0;
-        if (n_seq > 1 && even < K_AUTO_STEPS) {
+        if (n_seq > 1 && even < cap) {
             std::vector<SeqDraft> balanced;
             fs = fill(even, balanced);
             if (fs == BS_OK && balanced.size() == drafts.size()) drafts.swap(balanced);
@@ -1405,6 +1510,8 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             plan_rows(s, q, o, lim);
         } else if (plane_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {
             plan_direct(s, q, true);
+        } else if (chain_applicable(s, q.first_op, q.n_ops, nullptr)) {
+            plan_chain(s, q, o);
         } else {
             st = plan_lds(s, q, o, lim);
         }

@@ -139,4 +139,43 @@ bs_status launch_xrows2(const PoolRows2K &k, int32_t dtype, int64_t grid_n, int3
     return ok ? BS_OK : BS_ERR_UNSUPPORTED;
 }
 
+// Instances of the chain kernel compiled into the library: 3 x 3 max pooling (stride 1, padding 1) followed by
+// BatchNorm, ReLU (the blocks of Section 5.1), three to eight levels, float32 and bfloat16.
+bool xrows_chain_supported(const RowsChainK &k, int32_t dtype)
+{
+    if (!dtype_has_tables(dtype) || k.n_levels < 3 || k.n_levels > K_CHAIN_MAX || !rows_pool_is<RMax3s1p1>(k.pool)) return false;
+    for (int32_t l = 0; l < k.n_levels; ++l)
+        if (rows_ew_code(k.ew[l], k.n_ew) != RW_BN_RELU) return false;
+    return true;
+}
+
+template <int DT, int VEC>
+static bool xrows_chain_launch_t(const RowsChainK &k, dim3 grid, dim3 block, hipStream_t st)
+{
+    switch (k.n_levels) {
+    case 3: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 3><<<grid, block, 0, st>>>(k); return true;
+    case 4: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 4><<<grid, block, 0, st>>>(k); return true;
+    case 5: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 5><<<grid, block, 0, st>>>(k); return true;
+    case 6: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 6><<<grid, block, 0, st>>>(k); return true;
+    case 7: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 7><<<grid, block, 0, st>>>(k); return true;
+    case 8: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 8><<<grid, block, 0, st>>>(k); return true;
+    default: return false;
+    }
+}
+
+bs_status launch_xrows_chain(const RowsChainK &k, int32_t dtype, int64_t grid_n, int32_t threads, void *stream)
+{
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
+    const int32_t vec = xrows_vec(dtype);
+    // what the kernel assumes: rows of whole column blocks in one wave, chunks that cover the plane, whole work-groups
+    if (!xrows_chain_supported(k, dtype) || k.cbs < 1 || k.cbs > 64 || (int64_t)k.cbs * vec != k.W || k.spw != 64 / k.cbs ||
+        k.div_cbs.d != (uint32_t)k.cbs || k.div_chunks.d != (uint32_t)k.chunks || k.div_c.d != (uint32_t)k.C || threads < 64 ||
+        threads % 64 != 0 || k.rc < 1 || (int64_t)k.chunks * k.rc < k.H || grid_n * (threads / 64) * k.spw < (int64_t)k.units)
+        return BS_ERR_UNSUPPORTED;
+    const bool ok = dtype == BS_BF16 ? xrows_chain_launch_t<DT_BF16, K_XROWS_VEC16>(k, grid, block, st)
+                                     : xrows_chain_launch_t<DT_F32, K_XROWS_VEC32>(k, grid, block, st);
+    return ok ? BS_OK : BS_ERR_UNSUPPORTED;
+}
+
 }  // namespace bs

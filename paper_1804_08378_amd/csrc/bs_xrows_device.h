@@ -629,4 +629,98 @@ __global__ __launch_bounds__(256) void pool_xrows2_kernel(const PoolRows2K k)
     }
 }
 
+// =============================================================================
+// pool_xrows_chain_kernel: L identical max-pooling steps that keep the plane's size, each followed by
+// the element-wise list EW (the blocks of Section 5.1's stacked-pooling experiment), in registers.
+// One new input row per step ripples through all L levels: level l's row h - l * PH needs level
+// l - 1's rows up to h - (l - 1) * PH, the one the same step has just produced.  Per level the lane
+// keeps the KH newest rows of the level below (own columns only: the maximum goes down the window's
+// rows first, then one row of column maxima is exchanged with the neighbouring lanes); the loop
+// body is unrolled KH times, so a row's place in its ring is known at compile time and nothing is
+// moved.  A chunk of rc output rows starts L * PH rows above its first row; the rows computed
+// before a level has seen KH real rows are never used by a row the chunk stores.
+// =============================================================================
+template <int DT, int VEC, class P, int EW, int L>
+__global__ __launch_bounds__(256) void pool_xrows_chain_kernel(const RowsChainK k)
+{
+    constexpr int KH = P::kh, KW = P::kw, PH = P::ph, PW = P::pw;
+    static_assert(P::kind == OP_MAXPOOL && P::sh == 1 && P::sw == 1 && KH == 2 * PH + 1 && KW == 2 * PW + 1 && PW <= VEC && L >= 1,
+                  "max pooling that keeps the plane's size");
+    using E = RowsEw<EW>;
+    using Row = XRowRaw<DT, VEC>;
+    constexpr int ES = DT != DT_F32 ? 2 : 4;
+    const float pad = -INFINITY;
+
+    const XLane lane = xrows_lane(k);
+    RowsParams<E> par[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) rows_load_params<E>(k.ew[l], k.params, k.C, lane.c, par[l]);
+    const char *inp = static_cast<const char *>(image_base<DT>(k.in, lane.img, k.in_extra)) + (size_t)lane.plane * (size_t)(k.H * k.W) * ES;
+    void *outp = image_base<DT>(k.out, lane.img, k.out_extra);
+    const int32_t col0 = lane.j * VEC;
+    const bool has_left = lane.j > 0, has_right = lane.j + 1 < k.cbs;
+    const uint32_t plane_off = lane.plane * (uint32_t)(k.H * k.W);
+    const int32_t o0 = lane.chunk * k.rc, o1 = min(o0 + k.rc, k.H);  // output rows of the chunk
+    const int32_t h_first = o0 - L * PH;                              // first input row the chunk needs
+    const int32_t passes = (k.rc + 2 * L * PH + KH - 1) / KH;         // the same for every lane
+
+    float ring[L][KH][VEC];  // ring[l]: the KH newest rows of level l (level 0: the input)
+#pragma unroll
+    for (int l = 0; l < L; ++l)
+#pragma unroll
+        for (int j = 0; j < KH; ++j)
+#pragma unroll
+            for (int n = 0; n < VEC; ++n) ring[l][j][n] = pad;
+
+    // the KH input rows of a pass are requested one pass ahead (never under a branch: a row outside the plane is
+    // requested from the nearest row inside and replaced by padding)
+    Row ahead[KH];
+#pragma unroll
+    for (int j = 0; j < KH; ++j) xrows_fetch<DT, VEC>(inp, h_first + j, k.H, k.W, col0, ahead[j]);
+    for (int32_t pass = 0; pass < passes; ++pass) {
+        Row now[KH];
+#pragma unroll
+        for (int j = 0; j < KH; ++j) now[j] = ahead[j];
+#pragma unroll
+        for (int j = 0; j < KH; ++j) xrows_fetch<DT, VEC>(inp, h_first + (pass + 1) * KH + j, k.H, k.W, col0, ahead[j]);
+#pragma unroll
+        for (int j = 0; j < KH; ++j) {
+            const int32_t h = h_first + pass * KH + j;
+            {
+                float x[VEC];
+                xrows_unpack<DT, VEC>(now[j], x);
+                const bool ok = h >= 0 && h < k.H;
+#pragma unroll
+                for (int n = 0; n < VEC; ++n) ring[0][j][n] = ok ? x[n] : pad;
+            }
+#pragma unroll
+            for (int l = 1; l <= L; ++l) {
+                const int32_t r = h - l * PH;  // the row of level l this step completes
+                float m[VEC], full[PW + VEC + PW], v[VEC];
+#pragma unroll
+                for (int n = 0; n < VEC; ++n) {
+                    m[n] = ring[l - 1][0][n];
+#pragma unroll
+                    for (int d = 1; d < KH; ++d) m[n] = __builtin_fmaxf(m[n], ring[l - 1][d][n]);
+                }
+                with_neighbours<VEC, PW, PW>(m, full, has_left, has_right, pad);
+#pragma unroll
+                for (int n = 0; n < VEC; ++n) {
+                    v[n] = full[n];
+#pragma unroll
+                    for (int d = 1; d < KW; ++d) v[n] = __builtin_fmaxf(v[n], full[n + d]);
+                }
+                rows_apply<DT, E, VEC>(v, par[l - 1]);
+                const bool rok = r >= 0 && r < k.H;
+                if (l < L) {
+#pragma unroll
+                    for (int n = 0; n < VEC; ++n) ring[l < L ? l : 0][j][n] = rok ? v[n] : pad;
+                } else if (lane.live && r >= o0 && r < o1) {
+                    store_elems<DT, VEC>(outp, plane_off + (uint32_t)(r * k.W + col0), v);
+                }
+            }
+        }
+    }
+}
+
 }  // namespace bs

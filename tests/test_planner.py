@@ -160,10 +160,29 @@ def test_halo_grows_with_every_block_and_forces_a_new_sequence():
         if info["n_sequences"] == 1:
             lds.append(q["lds_bytes"])
             halos.append((q["halo_rows"], q["halo_cols"]))
-        seqs.append(plan(_blocks(n), shape, max_lds_bytes=8192)["n_sequences"])
+        seqs.append(plan(_blocks(n), shape, max_lds_bytes=8192, force_variant=bs.BS_VARIANT_LDS_TILE)["n_sequences"])
     assert all(b > a for a, b in zip(lds, lds[1:]))
     assert [h[0] for h in halos] == [2 * (i + 1) for i in range(len(halos))]  # k=3, s=1: +2 rows per block
     assert seqs[0] == 1 and seqs[-1] > 1 and all(b >= a for a, b in zip(seqs, seqs[1:]))
+
+
+def test_chains_of_identical_blocks_take_the_register_kernel():
+    """Three to eight blocks <MaxPool 3/1/1, BatchNorm, ReLU> on rows that fit a wave: one sequence without LDS
+    whatever the on-chip budget, as many levels as the kernel is compiled for, chunks of half the plane; longer
+    stacks are cut into sequences of even length."""
+    shape = (2, 4, 56, 56)
+    for n in (3, 5, 8):
+        info = plan(_blocks(n), shape, max_lds_bytes=8192)
+        q = info["sequences"][0]
+        assert info["n_sequences"] == 1 and q["variant"] == bs.BS_VARIANT_ROWS_CHAIN and q["lds_bytes"] == 0
+        assert q["n_steps"] == n and q["tile_rows"] == 28 and q["halo_rows"] == 2 * n
+    assert [q["n_steps"] for q in plan(_blocks(12), shape)["sequences"]] == [6, 6]
+    assert [q["n_steps"] for q in plan(_blocks(20), shape)["sequences"]] == [7, 7, 6]
+    # two blocks: the two-level kernel; binary16, rows too wide for a wave or no lane exchange: the LDS tiles
+    assert plan(_blocks(2), shape)["sequences"][0]["variant"] == bs.BS_VARIANT_POOL_ROWS
+    assert plan(_blocks(4), shape, "f16")["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
+    assert plan(_blocks(4), (1, 4, 8, 512))["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
+    assert plan(_blocks(4), shape, lane_exchange=-1)["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
 
 
 def test_lds_budget_is_respected_and_no_fit_is_reported():
