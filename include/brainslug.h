@@ -138,7 +138,7 @@ typedef enum bs_variant {
     BS_VARIANT_NHWC_STREAM = 6, /* channels-last plans only: element-wise, one channel vector per lane   */
     BS_VARIANT_NHWC_POOL = 7,   /* channels-last plans only: one pooling step, a lane = one output pixel x one channel vector */
     BS_VARIANT_NHWC_TILE = 8,   /* channels-last plans only: two pooling steps, tiles of both planes with halos staged in LDS */
-    BS_VARIANT_ROWS_CHAIN = 9   /* three and more identical max-pooling steps that keep the plane's size, each with the same
+    BS_VARIANT_ROWS_CHAIN = 9   /* two and more identical max-pooling steps that keep the plane's size, each with the same
                                    kinds of element-wise operations behind it: rows ripple through all levels in registers */
 } bs_variant;
 

@@ -203,7 +203,7 @@ struct RowsChainK {
     void *out;
     const float *params;
     uint32_t in_extra, out_extra;  // elements to skip per image beyond a dense one: batch stride - C*H*W (0 = dense)
-    int32_t n_levels;              // pooling steps, 3 .. K_CHAIN_MAX
+    int32_t n_levels;              // pooling steps, 1 .. K_CHAIN_MAX
     int32_t n_ew;                  // element-wise operations behind each of them
     EwOp ew[K_CHAIN_MAX][K_MAX_EW];
     PoolK pool;

@@ -336,6 +336,11 @@ static bool direct_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops
 static bool rows_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill);
 static bool plane_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops);
 static bool chain_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops, Sequence *fill);
+// Fewest identical pooling blocks the chain kernel is used for.  Measured on 64 x 64 x 56 x 56, float32: one block 25 us
+// (one-level sliding-window kernel: 22 us), two blocks 25 us (two-level kernel: 34 us), three 26 us, four 27 us.
+#if !defined(BS_CHAIN_MIN)
+#define BS_CHAIN_MIN 2
+#endif
 
 static uint64_t seq_min_lds(const bs_stack *s, int32_t first_op, int32_t n_ops, int32_t threads)
 {
@@ -900,7 +905,7 @@ static void plan_exchange(Sequence &q, K &k, int64_t planes, int32_t rc, int32_t
     q.grid = ((int64_t)k.units + per_group - 1) / per_group;
 }
 
-// Three and more identical max-pooling steps that keep the plane's size (odd window, stride 1, padding (k - 1) / 2,
+// Two and more identical max-pooling steps that keep the plane's size (odd window, stride 1, padding (k - 1) / 2,
 // no index output), each followed by element-wise operations of the same kinds (no Add), nothing in front of the
 // first: the blocks of Section 5.1.  The chain kernel exists for the shapes and lists compiled into the library, on
 // planes whose rows fit one wave; anything else takes the LDS tiles.
@@ -936,7 +941,7 @@ static bool chain_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
             if (level == 0) k.n_ew = n_here;
         }
     }
-    if (level < 2 || n_here != k.n_ew) return false;
+    if (level < BS_CHAIN_MIN - 1 || n_here != k.n_ew) return false;
     k.n_levels = level + 1;
     const int32_t vec = xrows_vec(s->dtype);
     if (!exchange_fits(s, k.W, vec) || !xrows_chain_supported(k, s->dtype)) return false;
@@ -1465,8 +1470,8 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             for (const SeqDraft &d : longer) {
                 int32_t fo, no;
                 range_ops(d, fo, no);
-                all_chains = all_chains && (d.n_steps < 3 || chain_applicable(s, fo, no, nullptr));
-                all_chains = all_chains && (d.n_steps >= 3 || longer.size() > 1);
+                all_chains = all_chains && (d.n_steps < BS_CHAIN_MIN || chain_applicable(s, fo, no, nullptr));
+                all_chains = all_chains && (d.n_steps >= BS_CHAIN_MIN || longer.size() > 1);
             }
             if (all_chains) cap = K_CHAIN_MAX;
         }
@@ -1506,6 +1511,8 @@ bs_status group_sequences(bs_stack *s, const bs_plan_options &o, const Limits &l
             plan_stream(s, q);
         } else if (direct_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {
             plan_direct(s, q);
+        } else if (BS_CHAIN_MIN < 3 && o.force_variant == BS_VARIANT_AUTO && chain_applicable(s, q.first_op, q.n_ops, nullptr)) {
+            plan_chain(s, q, o);
         } else if (rows_applicable(s, q.first_op, q.n_ops, nullptr) && o.force_variant != BS_VARIANT_LDS_TILE) {
             plan_rows(s, q, o, lim);
         } else if (plane_applicable(s, q.first_op, q.n_ops) && o.force_variant != BS_VARIANT_LDS_TILE) {

@@ -143,7 +143,7 @@ bs_status launch_xrows2(const PoolRows2K &k, int32_t dtype, int64_t grid_n, int3
 // BatchNorm, ReLU (the blocks of Section 5.1), three to eight levels, float32 and bfloat16.
 bool xrows_chain_supported(const RowsChainK &k, int32_t dtype)
 {
-    if (!dtype_has_tables(dtype) || k.n_levels < 3 || k.n_levels > K_CHAIN_MAX || !rows_pool_is<RMax3s1p1>(k.pool)) return false;
+    if (!dtype_has_tables(dtype) || k.n_levels < 1 || k.n_levels > K_CHAIN_MAX || !rows_pool_is<RMax3s1p1>(k.pool)) return false;
     for (int32_t l = 0; l < k.n_levels; ++l)
         if (rows_ew_code(k.ew[l], k.n_ew) != RW_BN_RELU) return false;
     return true;
@@ -153,6 +153,8 @@ template <int DT, int VEC>
 static bool xrows_chain_launch_t(const RowsChainK &k, dim3 grid, dim3 block, hipStream_t st)
 {
     switch (k.n_levels) {
+    case 1: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 1><<<grid, block, 0, st>>>(k); return true;
+    case 2: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 2><<<grid, block, 0, st>>>(k); return true;
     case 3: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 3><<<grid, block, 0, st>>>(k); return true;
     case 4: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 4><<<grid, block, 0, st>>>(k); return true;
     case 5: pool_xrows_chain_kernel<DT, VEC, RMax3s1p1, RW_BN_RELU, 5><<<grid, block, 0, st>>>(k); return true;

@@ -167,7 +167,7 @@ def test_halo_grows_with_every_block_and_forces_a_new_sequence():
 
 
 def test_chains_of_identical_blocks_take_the_register_kernel():
-    """Three to eight blocks <MaxPool 3/1/1, BatchNorm, ReLU> on rows that fit a wave: one sequence without LDS
+    """Two to eight blocks <MaxPool 3/1/1, BatchNorm, ReLU> on rows that fit a wave: one sequence without LDS
     whatever the on-chip budget, as many levels as the kernel is compiled for, chunks of half the plane; longer
     stacks are cut into sequences of even length."""
     shape = (2, 4, 56, 56)
@@ -178,8 +178,9 @@ def test_chains_of_identical_blocks_take_the_register_kernel():
         assert q["n_steps"] == n and q["tile_rows"] == 28 and q["halo_rows"] == 2 * n
     assert [q["n_steps"] for q in plan(_blocks(12), shape)["sequences"]] == [6, 6]
     assert [q["n_steps"] for q in plan(_blocks(20), shape)["sequences"]] == [7, 7, 6]
-    # two blocks: the two-level kernel; binary16, rows too wide for a wave or no lane exchange: the LDS tiles
-    assert plan(_blocks(2), shape)["sequences"][0]["variant"] == bs.BS_VARIANT_POOL_ROWS
+    # one block: the one-level kernel; two: the chain; binary16, rows too wide for a wave or no lane exchange: the LDS tiles
+    assert plan(_blocks(1), shape)["sequences"][0]["variant"] == bs.BS_VARIANT_POOL_ROWS
+    assert plan(_blocks(2), shape)["sequences"][0]["variant"] == bs.BS_VARIANT_ROWS_CHAIN
     assert plan(_blocks(4), shape, "f16")["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
     assert plan(_blocks(4), (1, 4, 8, 512))["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
     assert plan(_blocks(4), shape, lane_exchange=-1)["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
