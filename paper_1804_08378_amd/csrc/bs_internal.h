@@ -200,6 +200,9 @@ bs_status launch_xrows(const PoolRowsK &k, int32_t dtype, int64_t grid, int32_t 
 bs_status launch_xrows2(const PoolRows2K &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
 // the chain kernel: is there an instance for this pooling shape, list and depth / launch it
 bool xrows_chain_supported(const RowsChainK &k, int32_t dtype);
+bool xrows_chain_buildable(const RowsChainK &k, int32_t vec);
+bool xrows_chain_launchable(const RowsChainK &k, int32_t dtype, int64_t grid, int32_t threads);
+std::string xrows_chain_expr(const RowsChainK &k, int32_t dtype);
 bs_status launch_xrows_chain(const RowsChainK &k, int32_t dtype, int64_t grid, int32_t threads, void *stream);
 // bs_lds.hip
 bool lds_fast_path(const LdsSeqK &k);

@@ -664,7 +664,8 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         RowsChainK k = q.chain;
         k.in = in; k.out = out; k.params = s->dev_params;
         k.in_extra = in_extra; k.out_extra = out_extra;
-        const bs_status ls = launch_xrows_chain(k, dtype, q.grid, q.threads, stream);
+        if (!xrows_chain_launchable(k, dtype, q.grid, q.threads)) return BS_ERR_UNSUPPORTED;
+        const bs_status ls = q.jit ? launch_built(q, false, &k, sizeof k, stream) : launch_xrows_chain(k, dtype, q.grid, q.threads, stream);
         if (ls != BS_OK) return ls;
         break;
     }

@@ -944,7 +944,8 @@ static bool chain_applicable(const bs_stack *s, int32_t first_op, int32_t n_ops,
     if (level < BS_CHAIN_MIN - 1 || n_here != k.n_ew) return false;
     k.n_levels = level + 1;
     const int32_t vec = xrows_vec(s->dtype);
-    if (!exchange_fits(s, k.W, vec) || !xrows_chain_supported(k, s->dtype)) return false;
+    if (!exchange_fits(s, k.W, vec)) return false;
+    if (!xrows_chain_supported(k, s->dtype) && !(jit_allowed(s) && xrows_chain_buildable(k, vec))) return false;
     k.cbs = k.W / vec;
     k.spw = 64 / k.cbs;
     if (fill) fill->chain = k;
@@ -1321,6 +1322,10 @@ static bool audit_lds(const Sequence &q)
 // Header and template-instance names (without / with index outputs) of a sequence's run-time build.
 static const char *jit_names(const bs_stack *s, const Sequence &q, std::string (&expr)[2])
 {
+    if (q.variant == BS_VARIANT_ROWS_CHAIN) {
+        expr[0] = expr[1] = xrows_chain_expr(q.chain, s->dtype);
+        return "bs_xrows_device.h";
+    }
     for (int w = 0; w < 2; ++w) {
         if (q.variant == BS_VARIANT_POOL_ROWS && q.n_levels == 2)
             expr[w] = q.rows2.spw > 0 ? xrows2_expr(q.rows2, s->dtype, w != 0) : rows2_expr(q.rows2, s->dtype, w != 0);
@@ -1353,6 +1358,9 @@ static bs_status prepare_jit(bs_stack *s, Sequence &q, bool host_only)
     } else if (q.variant == BS_VARIANT_POOL_ROWS) {
         const PoolRowsK &k = q.rows;
         if (tables && rows_supported(k.pool, k.pre, k.n_pre, k.post, k.n_post)) return BS_OK;
+    } else if (q.variant == BS_VARIANT_ROWS_CHAIN) {
+        if (q.vec != xrows_vec(s->dtype)) return BS_ERR_UNSUPPORTED;
+        if (xrows_chain_supported(q.chain, s->dtype)) return BS_OK;
     } else if (q.variant == BS_VARIANT_LDS_TILE) {
         if (lds_precompiled(q.lds, s->dtype) || !jit_allowed(s) || !lds_buildable(q.lds)) return BS_OK;
     } else {

@@ -149,6 +149,39 @@ bool xrows_chain_supported(const RowsChainK &k, int32_t dtype)
     return true;
 }
 
+// Can the chain kernel be instantiated for this chain (a run-time build)?  Max pooling with an odd window, stride 1,
+// padding (k - 1) / 2, edge columns from the adjacent lanes only, every level the same list without Add, and rings
+// (levels x window rows x columns) that stay in registers.
+bool xrows_chain_buildable(const RowsChainK &k, int32_t vec)
+{
+    const PoolK &p = k.pool;
+    if (k.n_levels < 1 || k.n_levels > K_CHAIN_MAX || p.kind != OP_MAXPOOL || p.sh != 1 || p.sw != 1 || p.kh != 2 * p.ph + 1 ||
+        p.kw != 2 * p.pw + 1 || p.pw > vec || p.kh > 7)
+        return false;
+    const int code = rows_ew_code(k.ew[0], k.n_ew);
+    if (code < 0) return false;
+    for (int32_t l = 1; l < k.n_levels; ++l)
+        if (rows_ew_code(k.ew[l], k.n_ew) != code) return false;
+    return k.n_levels * p.kh * vec <= 200;
+}
+
+std::string xrows_chain_expr(const RowsChainK &k, int32_t dtype)
+{
+    char b[64];
+    std::snprintf(b, sizeof b, ", %d, %d>", rows_ew_code(k.ew[0], k.n_ew), k.n_levels);
+    return std::string("bs::pool_xrows_chain_kernel<") + std::to_string(dtype) + ", " + std::to_string(xrows_vec(dtype)) + ", " +
+           spec_expr(k.pool) + b;
+}
+
+// What the chain kernel assumes about its argument block and launch.
+bool xrows_chain_launchable(const RowsChainK &k, int32_t dtype, int64_t grid_n, int32_t threads)
+{
+    const int32_t vec = xrows_vec(dtype);
+    return k.cbs >= 1 && k.cbs <= 64 && (int64_t)k.cbs * vec == k.W && k.spw == 64 / k.cbs && k.div_cbs.d == (uint32_t)k.cbs &&
+           k.div_chunks.d == (uint32_t)k.chunks && k.div_c.d == (uint32_t)k.C && threads >= 64 && threads % 64 == 0 && k.rc >= 1 &&
+           (int64_t)k.chunks * k.rc >= k.H && grid_n * (threads / 64) * k.spw >= (int64_t)k.units;
+}
+
 template <int DT, int VEC>
 static bool xrows_chain_launch_t(const RowsChainK &k, dim3 grid, dim3 block, hipStream_t st)
 {
@@ -169,12 +202,8 @@ bs_status launch_xrows_chain(const RowsChainK &k, int32_t dtype, int64_t grid_n,
 {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((uint32_t)grid_n), block((uint32_t)threads);
-    const int32_t vec = xrows_vec(dtype);
     // what the kernel assumes: rows of whole column blocks in one wave, chunks that cover the plane, whole work-groups
-    if (!xrows_chain_supported(k, dtype) || k.cbs < 1 || k.cbs > 64 || (int64_t)k.cbs * vec != k.W || k.spw != 64 / k.cbs ||
-        k.div_cbs.d != (uint32_t)k.cbs || k.div_chunks.d != (uint32_t)k.chunks || k.div_c.d != (uint32_t)k.C || threads < 64 ||
-        threads % 64 != 0 || k.rc < 1 || (int64_t)k.chunks * k.rc < k.H || grid_n * (threads / 64) * k.spw < (int64_t)k.units)
-        return BS_ERR_UNSUPPORTED;
+    if (!xrows_chain_supported(k, dtype) || !xrows_chain_launchable(k, dtype, grid_n, threads)) return BS_ERR_UNSUPPORTED;
     const bool ok = dtype == BS_BF16 ? xrows_chain_launch_t<DT_BF16, K_XROWS_VEC16>(k, grid, block, st)
                                      : xrows_chain_launch_t<DT_F32, K_XROWS_VEC32>(k, grid, block, st);
     return ok ? BS_OK : BS_ERR_UNSUPPORTED;

@@ -343,7 +343,7 @@ def test_chains_of_identical_pooling_blocks_in_registers(shape, dtype):
     take (binary16 storage, lanes that must not exchange columns, an index output inside, other lists)."""
     c = shape[1]
     vec = 4 if dtype == "f32" else 8
-    chain = dtype != "f16" and shape[3] % vec == 0 and shape[3] // vec <= 64
+    chain = shape[3] % vec == 0 and shape[3] // vec <= 64  # binary16: a run-time build of the same kernel
     for blocks in (2, 3, 4, 5, 8):
         layers = sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 300 + i), wl.relu()] for i in range(blocks)), [])
         x = wl.activation(shape, 72, dtype)
@@ -357,11 +357,16 @@ def test_chains_of_identical_pooling_blocks_in_registers(shape, dtype):
             info = check(layers, x, [], dtype, f"chain/{blocks}{shape}/{opts}", max_steps_per_sequence=blocks, **opts)
             other = ("lds_tile", "pool_rows") if blocks == 2 and "lane_exchange" in opts else ("lds_tile",)
             assert all(q["variant_name"] in other for q in info["sequences"]), (blocks, opts)
-    # an index output inside the chain, a list in front of the first pooling, another list: the LDS tiles
+    # other lists and windows: run-time builds of the chain kernel
+    for layers in (sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 316 + i), wl.leaky_relu(0.1)] for i in range(3)), []),
+                   sum(([wl.maxpool(5, 1, 2), wl.clamp(-0.5, 1.0), wl.bn_params(c, 320 + i)] for i in range(4)), []),
+                   sum(([wl.maxpool((3, 1), 1, (1, 0))] for i in range(5)), [])):
+        info = check(layers, wl.activation(shape, 74, dtype), [], dtype, f"chain/built{shape}", max_steps_per_sequence=8)
+        assert [q["variant_name"] for q in info["sequences"]] == (["rows_chain"] if chain else ["lds_tile"] * info["n_sequences"])
+    # an index output inside the chain, a list in front of the first pooling: the LDS tiles
     for layers in ([wl.maxpool(3, 1, 1), wl.bn_params(c, 310), wl.relu(), wl.maxpool(3, 1, 1, True), wl.bn_params(c, 311), wl.relu(),
                     wl.maxpool(3, 1, 1), wl.bn_params(c, 312), wl.relu()],
-                   [wl.relu()] + sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 313 + i), wl.relu()] for i in range(3)), []),
-                   sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 316 + i), wl.leaky_relu(0.1)] for i in range(3)), [])):
+                   [wl.relu()] + sum(([wl.maxpool(3, 1, 1), wl.bn_params(c, 313 + i), wl.relu()] for i in range(3)), [])):
         info = check(layers, wl.activation(shape, 73, dtype), [], dtype, f"chain/not taken{shape}", max_steps_per_sequence=3)
         assert all(q["variant_name"] != "rows_chain" for q in info["sequences"])
 

@@ -50,6 +50,9 @@ def test_run_time_builds_compile_without_a_device():
         ([wl.maxpool(3, 2, 1), wl.bn_params(4, 1), wl.relu(), wl.avgpool(2, 2), wl.maxpool(3, 1, 1)],
          (2, 4, 64, 64), ["lds_tile"], 1),
         ([wl.bn_params(4, 2), wl.add(), wl.relu(), wl.maxpool(3, 2, 1)], (1, 4, 30, 30), ["lds_tile"], 1),
+        # chains of identical blocks with a list or a window that has no compiled instance
+        (sum(([wl.maxpool(3, 1, 1), wl.bn_params(4, 3 + i), wl.leaky_relu(0.1)] for i in range(4)), []), (2, 4, 32, 32), ["rows_chain"], 1),
+        (sum(([wl.maxpool(5, 1, 2), wl.clamp(-1.0, 1.0)] for i in range(3)), []), (2, 4, 32, 32), ["rows_chain"], 1),
     ]
     # ... without the exchange a lane of the rows kernel would compute 8 columns for 4 owned (float32)
     # or 12 for 8 (16-bit types); LDS shares them between lanes and wins in the first case
@@ -178,10 +181,12 @@ def test_chains_of_identical_blocks_take_the_register_kernel():
         assert q["n_steps"] == n and q["tile_rows"] == 28 and q["halo_rows"] == 2 * n
     assert [q["n_steps"] for q in plan(_blocks(12), shape)["sequences"]] == [6, 6]
     assert [q["n_steps"] for q in plan(_blocks(20), shape)["sequences"]] == [7, 7, 6]
-    # one block: the one-level kernel; two: the chain; binary16, rows too wide for a wave or no lane exchange: the LDS tiles
+    # one block: the one-level kernel; two: the chain; rows too wide for a wave or no lane exchange: the LDS tiles
     assert plan(_blocks(1), shape)["sequences"][0]["variant"] == bs.BS_VARIANT_POOL_ROWS
     assert plan(_blocks(2), shape)["sequences"][0]["variant"] == bs.BS_VARIANT_ROWS_CHAIN
-    assert plan(_blocks(4), shape, "f16")["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
+    f16 = plan(_blocks(4), shape, "f16")["sequences"][0]   # binary16: no compiled tables, a run-time build of the same kernel
+    assert f16["variant"] == bs.BS_VARIANT_ROWS_CHAIN and f16["run_time_build"] == 1
+    assert plan(_blocks(4), shape, "f16", jit=-1)["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
     assert plan(_blocks(4), (1, 4, 8, 512))["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
     assert plan(_blocks(4), shape, lane_exchange=-1)["sequences"][0]["variant"] == bs.BS_VARIANT_LDS_TILE
 
