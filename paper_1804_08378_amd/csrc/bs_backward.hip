@@ -480,7 +480,8 @@ __global__ __launch_bounds__(256) void bwd_ew_kernel(const BwdK k)
 // order, as the forward kernels do) and writes the gradients of all its cells.  No recorded
 // picks, no recomputation pass: the stage input and the gradient with respect to it move once.
 // =============================================================================
-template <int DT, int VEC, int NR>
+// PRE: the kinds of the stage's element-wise list as a compile-time code (ew_sweep_impl), or -1: read at run time.
+template <int DT, int VEC, int NR, int PRE = -1>
 __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
 {
     constexpr int NO = VEC / 2;
@@ -506,7 +507,8 @@ __global__ __launch_bounds__(256) void bwd_direct2_kernel(const BwdK k)
     unpack<DT, VEC>(a1, x[1]);
     unpack<DT, NO>(gr, g);
     const int32_t cs[2] = {c, c};
-    const int32_t adds = ew_sweep<DT, VEC, 2, false, NR>(k, cs, offs, x, t, r);
+    const uint32_t whole[2] = {};
+    const int32_t adds = ew_sweep_impl<DT, VEC, 2, false, NR, false, PRE>(k, cs, offs, x, t, r, whole, 0, k.n_ew);
 
     float s[2][VEC];
     if (k.pool.kind == OP_MAXPOOL) {
@@ -1270,9 +1272,12 @@ bs_status launch_backward_stage(const BwdK &k, int32_t dtype, int32_t vec, int64
         if ((p.kind != OP_MAXPOOL && p.kind != OP_AVGSUM) || p.kh != 2 || p.kw != 2 || p.sh != 2 || p.sw != 2 || p.ph != 0 ||
             p.pw != 0 || k.H != 2 * k.Ho || k.W != 2 * k.Wo || vec < 2)
             return BS_ERR_UNSUPPORTED;
+        // BatchNorm, ReLU in front of the pooling (the VGG stacks, the DenseNet transition): the kinds of the list compiled in
+        const bool bn_relu2 = k.n_ew == 2 && k.ew[0].kind == OP_BN && k.ew[1].kind == OP_RELU;
 #define BS_LAUNCH_DIRECT(DT, V)                                                                \
     do {                                                                                       \
-        if (n_add == 0) bwd_direct2_kernel<DT, V, 0><<<g, b, 0, st>>>(k);                      \
+        if (n_add == 0 && bn_relu2) bwd_direct2_kernel<DT, V, 0, OP_BN + OP_RELU * K_EW_BASE><<<g, b, 0, st>>>(k); \
+        else if (n_add == 0) bwd_direct2_kernel<DT, V, 0><<<g, b, 0, st>>>(k);                 \
         else if (n_add == 1) bwd_direct2_kernel<DT, V, 1><<<g, b, 0, st>>>(k);                 \
         else bwd_direct2_kernel<DT, V, K_MAX_RES><<<g, b, 0, st>>>(k);                         \
     } while (0)
