@@ -65,22 +65,8 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // FLAT (row-major only): nfirst[j] cells of row j lie in channel c[j], the rest in the next channel
 // (a vector that straddles two planes).  Otherwise every cell of row j lies in channel c[j].
 // The list is k.ew[first .. first + count).
-// CODE >= 0: the kinds of the list's operations are known at compile time (one base-K_EW_BASE digit per operation, the first in
-// the lowest digit; `count` is ignored) and the loop over the list unrolls into straight code; their arguments still come from k.ew.
-constexpr int ew_code_len(int code)
-{
-    int n = 0;
-    while (code > 0) {
-        ++n;
-        code /= K_EW_BASE;
-    }
-    return n;
-}
-constexpr int ew_code_kind(int code, int q)
-{
-    for (int i = 0; i < q; ++i) code /= K_EW_BASE;
-    return code % K_EW_BASE;
-}
+// CODE >= 0: the kinds of the list's operations are known at compile time (a code of base-K_EW_BASE digits; `count` is
+// ignored) and the loop over the list unrolls into straight code; their arguments still come from k.ew.
 
 template <int DT, int VEC, int R, bool CL, int NR, bool FLAT, int CODE = -1>
 BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC],

@@ -34,6 +34,21 @@ enum OpKind : int32_t {
 // Element-wise lists are packed into template arguments one base-K_EW_BASE digit per operation
 // (the operation kind; first operation in the lowest digit, 0 = end).
 constexpr int K_EW_BASE = 16;
+// number of operations in such a code, and the kind of its q-th operation
+constexpr int ew_code_len(int code)
+{
+    int n = 0;
+    while (code > 0) {
+        ++n;
+        code /= K_EW_BASE;
+    }
+    return n;
+}
+constexpr int ew_code_kind(int code, int q)
+{
+    for (int i = 0; i < q; ++i) code /= K_EW_BASE;
+    return code % K_EW_BASE;
+}
 
 inline bool op_is_elementwise(int32_t k) { return k != OP_MAXPOOL && k != OP_AVGSUM; }
 

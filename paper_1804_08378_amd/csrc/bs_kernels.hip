@@ -37,14 +37,14 @@ namespace bs {
 // no load here is predicated.
 //   c[u]    channel of vector u (BatchNorm parameters)
 //   off[u]  element offset of vector u in this level's tensors (residual loads)
-template <int DT, int VEC, int U>
+//   CODE    >= 0: the list's kinds as a code of base-K_EW_BASE digits (n_ew is ignored): the list unrolls into
+//           straight code and only the arguments come from `ew`; -1: kinds and length are read at run time
+template <int DT, int VEC, int U, int CODE = -1>
 BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (&off)[U],
                      const EwOp *ew, int32_t n_ew, const float *__restrict__ params, int32_t C,
                      const void *const *res)
 {
-#pragma clang loop unroll(disable)
-    for (int32_t j = 0; j < n_ew; ++j) {
-        const int32_t kind = ew[j].kind, arg = ew[j].arg;
+    auto one = [&](const int32_t kind, const int32_t arg) {
         if (kind == OP_BN) {
             float sc[U], sh[U];
 #pragma unroll
@@ -87,14 +87,22 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
                 for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(x[u][i] + r[i]);
             }
         }
+    };
+    if constexpr (CODE >= 0) {
+#pragma unroll
+        for (int j = 0; j < ew_code_len(CODE); ++j) one(ew_code_kind(CODE, j), ew[j].arg);
+    } else {
+#pragma clang loop unroll(disable)
+        for (int32_t j = 0; j < n_ew; ++j) one(ew[j].kind, ew[j].arg);
     }
 }
 
 // =============================================================================
 // stream_kernel: element-wise only sequence.  A work-group takes nthr * U
 // consecutive 128-bit vectors; lane t handles vectors t, t + nthr, ...
+// CODE: the kinds of the list's operations as a compile-time code (apply_ew), or -1.
 // =============================================================================
-template <int DT, int VEC, int U>
+template <int DT, int VEC, int U, int CODE = -1>
 __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
 {
     const uint32_t nthr = blockDim.x;
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(512) void stream_kernel(const StreamK k)
     float x[U][VEC];
 #pragma unroll
     for (int u = 0; u < U; ++u) unpack<DT, VEC>(raw[u], x[u]);
-    apply_ew<DT, VEC, U>(x, c, off, k.ew, k.n_ew, k.params, k.C, k.res);
+    apply_ew<DT, VEC, U, CODE>(x, c, off, k.ew, k.n_ew, k.params, k.C, k.res);
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (valid[u]) store_elems<DT, VEC>(image_base<DT>(k.out, img[u], k.out_extra), off[u], x[u]);
@@ -536,6 +544,19 @@ static bs_status launch_built(const Sequence &q, bool want_idx, const void *args
     return jit_launch(fn, args, bytes, q.grid, q.threads, q.lds_bytes, stream);
 }
 
+// stream_kernel with full-width vectors: the lists of the common networks -- BatchNorm, ReLU (DenseNet) and
+// BatchNorm, Add, ReLU (ResNet) -- are compiled in, any other list is read at run time.
+template <int DT, int VEC>
+static void launch_stream(const StreamK &k, dim3 grid, dim3 block, hipStream_t st)
+{
+    constexpr int BN_RELU = OP_BN + OP_RELU * K_EW_BASE, BN_ADD_RELU = OP_BN + (OP_ADD + OP_RELU * K_EW_BASE) * K_EW_BASE;
+    int32_t code = 0, digit = 1;
+    for (int32_t j = 0; j < k.n_ew && j < 4; ++j, digit *= K_EW_BASE) code += k.ew[j].kind * digit;
+    if (k.n_ew == 2 && code == BN_RELU) stream_kernel<DT, VEC, K_STREAM_U, BN_RELU><<<grid, block, 0, st>>>(k);
+    else if (k.n_ew == 3 && code == BN_ADD_RELU) stream_kernel<DT, VEC, K_STREAM_U, BN_ADD_RELU><<<grid, block, 0, st>>>(k);
+    else stream_kernel<DT, VEC, K_STREAM_U><<<grid, block, 0, st>>>(k);
+}
+
 bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, void *out,
                           uint32_t in_extra, uint32_t out_extra, const void *const *res,
                           int32_t *const *idx, void *stream)
@@ -579,13 +600,13 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
             break;
         }
         if (dtype == BS_BF16) {
-            if (q.vec == 8) stream_kernel<DT_BF16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            if (q.vec == 8) launch_stream<DT_BF16, 8>(k, grid, block, st);
             else stream_kernel<DT_BF16, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
         } else if (dtype == BS_F16) {
-            if (q.vec == 8) stream_kernel<DT_F16, 8, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            if (q.vec == 8) launch_stream<DT_F16, 8>(k, grid, block, st);
             else stream_kernel<DT_F16, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
         } else {
-            if (q.vec == 4) stream_kernel<DT_F32, 4, K_STREAM_U><<<grid, block, 0, st>>>(k);
+            if (q.vec == 4) launch_stream<DT_F32, 4>(k, grid, block, st);
             else stream_kernel<DT_F32, 1, K_STREAM_U><<<grid, block, 0, st>>>(k);
         }
         break;

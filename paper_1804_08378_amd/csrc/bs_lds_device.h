@@ -72,21 +72,12 @@ template <int CODE>
 struct EwList {
     static constexpr bool is_static = CODE >= 0;
     static constexpr int code = CODE;
-    __host__ __device__ static constexpr int count_static()
-    {
-        int n = 0, c = CODE < 0 ? 0 : CODE;
-        while (c) { ++n; c /= K_EW_BASE; }
-        return n;
-    }
+    __host__ __device__ static constexpr int count_static() { return ew_code_len(CODE); }
     static constexpr int slots = CODE >= 0 ? count_static() : K_MAX_EW;
     BS_DEV static int count(const LevelK &lv) { return CODE >= 0 ? count_static() : lv.n_ew; }
     BS_DEV static int kind(const LevelK &lv, int j)
     {
-        if (CODE >= 0) {
-            int c = CODE;
-            for (int i = 0; i < j; ++i) c /= K_EW_BASE;
-            return c % K_EW_BASE;  // digits are the operation kinds
-        }
+        if (CODE >= 0) return ew_code_kind(CODE, j);  // digits are the operation kinds
         return lv.ew[j].kind;
     }
 };

@@ -26,8 +26,8 @@
 namespace bs {
 
 // Element-wise only.  A work-group takes nthr * U consecutive vectors; lane t handles vectors
-// t, t + nthr, ...
-template <int DT, int VEC, int U>
+// t, t + nthr, ...  CODE: the kinds of the list's operations as a compile-time code (apply_ew_nhwc), or -1.
+template <int DT, int VEC, int U, int CODE = -1>
 __global__ __launch_bounds__(512) void nhwc_stream_kernel(const NhwcK k)
 {
     const uint32_t nthr = blockDim.x;
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(512) void nhwc_stream_kernel(const NhwcK k)
         float x[U][VEC];
 #pragma unroll
         for (int u = 0; u < U; ++u) unpack<DT, VEC>(raw[u], x[u]);
-        apply_ew_nhwc<DT, VEC, U>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
+        apply_ew_nhwc<DT, VEC, U, CODE>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (valid[u]) store_elems<DT, VEC>(k.out, off[u] + pixel[u] * k.out_xp, x[u]);
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(512) void nhwc_stream_kernel(const NhwcK k)
         const uint32_t c0 = (i - pixel * cvn) * VEC;
         float x[1][VEC];
         unpack<DT, VEC>(load_raw<DT, VEC, true>(k.in, off1[0] + pixel * k.in_xp), x[0]);
-        apply_ew_nhwc<DT, VEC, 1>(x, c0, off1, k.pre, k.n_pre, k.params, k.C, k.res);
+        apply_ew_nhwc<DT, VEC, 1, CODE>(x, c0, off1, k.pre, k.n_pre, k.params, k.C, k.res);
         if (valid) store_elems<DT, VEC>(k.out, off1[0] + pixel * k.out_xp, x[0]);
     }
 }
@@ -100,7 +100,8 @@ BS_DEV void take_cell(bool is_max, const float (&v)[VEC], int32_t cell_index, fl
 // the element-wise operations before the pool run once per cell (not once per window that
 // holds it), then every output of the block takes its window from the registers.
 // IDX: keep the argmax (only when an index output was asked for).
-template <int DT, int VEC, int KH, int KW, int SH, int SW, int OHB, int OWB, bool IDX>
+// PRE, POST: the kinds of the lists in front of and behind the pooling as compile-time codes (apply_ew_nhwc), or -1.
+template <int DT, int VEC, int KH, int KW, int SH, int SW, int OHB, int OWB, bool IDX, int PRE = -1, int POST = -1>
 __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
 {
     constexpr int CR = (OHB - 1) * SH + KH, CC = (OWB - 1) * SW + KW, NCELL = CR * CC, NOUT = OHB * OWB;
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
                 unpack<DT, VEC>(raw[dh * CC + dw], xr[dw]);
                 offr[dw] = off[dh * CC + dw];
             }
-            apply_ew_nhwc<DT, VEC, KW>(xr, c0, offr, k.pre, k.n_pre, k.params, k.C, k.res);
+            apply_ew_nhwc<DT, VEC, KW, PRE>(xr, c0, offr, k.pre, k.n_pre, k.params, k.C, k.res);
 #pragma unroll
             for (int dw = 0; dw < KW; ++dw)
                 if (interior || (hb + dh >= hlo && hb + dh < hhi && wb + dw >= wlo && wb + dw < whi))
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) y[0][e] = round_store<DT>(acc[e] * inv);
         }
-        apply_ew_nhwc<DT, VEC, 1>(y, c0, ooff, k.post, k.n_post, k.params, k.C, k.res);
+        apply_ew_nhwc<DT, VEC, 1, POST>(y, c0, ooff, k.post, k.n_post, k.params, k.C, k.res);
         if (live && oin) {
             store_elems<DT, VEC>(k.out, ooff[0] + opix * k.out_xp, y[0]);
             if constexpr (IDX) {
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
 #pragma unroll
         for (int cell = 0; cell < NCELL; ++cell) unpack<DT, VEC>(raw[cell], x[cell]);
     }
-    apply_ew_nhwc<DT, VEC, NCELL>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
+    apply_ew_nhwc<DT, VEC, NCELL, PRE>(x, c0, off, k.pre, k.n_pre, k.params, k.C, k.res);
 
     float y[NOUT][VEC];
     int32_t yi[NOUT][VEC];
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(256) void nhwc_pool_kernel(const NhwcK k)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) yi[o][e] = bi[e];
         }
-    apply_ew_nhwc<DT, VEC, NOUT>(y, c0, ooff, k.post, k.n_post, k.params, k.C, k.res);
+    apply_ew_nhwc<DT, VEC, NOUT, POST>(y, c0, ooff, k.post, k.n_post, k.params, k.C, k.res);
 #pragma unroll
     for (int o = 0; o < NOUT; ++o)
         if (live && oin[o]) {
@@ -426,10 +427,34 @@ void nhwc_block(const PoolK &p, int32_t vec, int32_t dtype, int32_t &ohb, int32_
     }
 }
 
-template <int DT, int VEC, int KH, int KW, int SH, int SW, int OHB, int OWB>
+// code of an element-wise list (-1: too long for a code)
+static int32_t list_code(const EwOp *ew, int32_t n)
+{
+    int32_t c = 0, digit = 1;
+    if (n > 6) return -1;
+    for (int32_t j = 0; j < n; ++j, digit *= K_EW_BASE) c += ew[j].kind * digit;
+    return c;
+}
+
+// COMMON: also the instances with the lists of the common networks compiled in -- BatchNorm, ReLU behind the pooling
+// (where the plan moved the list behind a max pooling: VGG, the ResNet stem) or in front of it (the DenseNet transition).
+template <int DT, int VEC, int KH, int KW, int SH, int SW, int OHB, int OWB, bool COMMON = false>
 static void launch_block(const NhwcK &k, dim3 grid, dim3 block, hipStream_t st)
 {
-    if (k.idx && k.pool.kind == OP_MAXPOOL) nhwc_pool_kernel<DT, VEC, KH, KW, SH, SW, OHB, OWB, true><<<grid, block, 0, st>>>(k);
+    constexpr int BN_RELU = OP_BN + OP_RELU * K_EW_BASE;
+    const bool idx = k.idx && k.pool.kind == OP_MAXPOOL;
+    if constexpr (COMMON) {
+        const int32_t pre = list_code(k.pre, k.n_pre), post = list_code(k.post, k.n_post);
+        if (!idx && pre == 0 && post == BN_RELU) {
+            nhwc_pool_kernel<DT, VEC, KH, KW, SH, SW, OHB, OWB, false, 0, BN_RELU><<<grid, block, 0, st>>>(k);
+            return;
+        }
+        if (!idx && pre == BN_RELU && post == 0) {
+            nhwc_pool_kernel<DT, VEC, KH, KW, SH, SW, OHB, OWB, false, BN_RELU, 0><<<grid, block, 0, st>>>(k);
+            return;
+        }
+    }
+    if (idx) nhwc_pool_kernel<DT, VEC, KH, KW, SH, SW, OHB, OWB, true><<<grid, block, 0, st>>>(k);
     else nhwc_pool_kernel<DT, VEC, KH, KW, SH, SW, OHB, OWB, false><<<grid, block, 0, st>>>(k);
 }
 
@@ -438,7 +463,12 @@ static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 bl
 {
     const PoolK &p = k.pool;
     if (p.kind == 0) {
-        nhwc_stream_kernel<DT, VEC, K_STREAM_U><<<grid, block, 0, st>>>(k);
+        // the lists of the common networks compiled in: BatchNorm, ReLU (DenseNet) and BatchNorm, Add, ReLU (ResNet)
+        constexpr int BN_RELU = OP_BN + OP_RELU * K_EW_BASE, BN_ADD_RELU = OP_BN + (OP_ADD + OP_RELU * K_EW_BASE) * K_EW_BASE;
+        const int32_t code = VEC > 1 ? list_code(k.pre, k.n_pre) : -1;
+        if (code == BN_RELU) nhwc_stream_kernel<DT, VEC, K_STREAM_U, BN_RELU><<<grid, block, 0, st>>>(k);
+        else if (code == BN_ADD_RELU) nhwc_stream_kernel<DT, VEC, K_STREAM_U, BN_ADD_RELU><<<grid, block, 0, st>>>(k);
+        else nhwc_stream_kernel<DT, VEC, K_STREAM_U><<<grid, block, 0, st>>>(k);
         return BS_OK;
     }
     if (k.cv_group > 0) {
@@ -459,10 +489,10 @@ static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 bl
         return BS_ERR_UNSUPPORTED;
     constexpr bool WIDE = VEC <= 4;
     if (p.kh == 2 && p.kw == 2 && p.sh == 2 && p.sw == 2) {
-        launch_block<DT, VEC, 2, 2, 2, 2, 1, 1>(k, grid, block, st);
+        launch_block<DT, VEC, 2, 2, 2, 2, 1, 1, (VEC > 1)>(k, grid, block, st);
     } else if (p.kh == 3 && p.kw == 3 && p.sh == 2 && p.sw == 2) {
         if (ohb != 1 || owb != 1) return BS_ERR_UNSUPPORTED;
-        launch_block<DT, VEC, 3, 3, 2, 2, 1, 1>(k, grid, block, st);
+        launch_block<DT, VEC, 3, 3, 2, 2, 1, 1, (VEC > 1)>(k, grid, block, st);
     } else if (p.kh == 3 && p.kw == 3 && p.sh == 1 && p.sw == 1) {
         if (ohb != 2 || owb != (WIDE ? 2 : 1)) return BS_ERR_UNSUPPORTED;
         launch_block<DT, VEC, 3, 3, 1, 1, 2, WIDE ? 2 : 1>(k, grid, block, st);

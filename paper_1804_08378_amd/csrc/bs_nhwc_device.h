@@ -25,14 +25,14 @@ BS_DEV void load_params(const float *__restrict__ params, uint32_t off, float (&
 // Apply an element-wise list to U register vectors that all hold channels c0 .. c0 + VEC - 1.
 //   off[u]  element offset of vector u in this level's tensors (residual loads), counted from
 //           element res_base (the same for all lanes)
-template <int DT, int VEC, int U>
+//   CODE    >= 0: the list's kinds as a code of base-K_EW_BASE digits (n_ew is ignored): the list unrolls into
+//           straight code and only the arguments come from `ew`; -1: kinds and length are read at run time
+template <int DT, int VEC, int U, int CODE = -1>
 BS_DEV void apply_ew_nhwc(float (&x)[U][VEC], uint32_t c0, const uint32_t (&off)[U], const EwOp *ew,
                           int32_t n_ew, const float *__restrict__ params, int32_t C, const void *const *res,
                           uint32_t res_base = 0)
 {
-#pragma clang loop unroll(disable)
-    for (int32_t j = 0; j < n_ew; ++j) {
-        const int32_t kind = ew[j].kind, arg = ew[j].arg;
+    auto one = [&](const int32_t kind, const int32_t arg) {
         if (kind == OP_BN) {
             float sc[VEC], sh[VEC];
             load_params<VEC>(params, (uint32_t)arg + c0, sc);
@@ -72,6 +72,13 @@ BS_DEV void apply_ew_nhwc(float (&x)[U][VEC], uint32_t c0, const uint32_t (&off)
                 for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(x[u][i] + r[i]);
             }
         }
+    };
+    if constexpr (CODE >= 0) {
+#pragma unroll
+        for (int j = 0; j < ew_code_len(CODE); ++j) one(ew_code_kind(CODE, j), ew[j].arg);
+    } else {
+#pragma clang loop unroll(disable)
+        for (int32_t j = 0; j < n_ew; ++j) one(ew[j].kind, ew[j].arg);
     }
 }
 

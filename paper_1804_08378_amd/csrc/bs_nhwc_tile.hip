@@ -166,22 +166,8 @@ constexpr int block_edge(int K, int S) { return K == 3 && S == 1 ? 2 : 1; }
 // vectors taken from the copies staged in LDS (`par`: the lane's vector of the list's first
 // BatchNorm scale; scale and shift of one operation, and operations, `stride` floats apart).
 //   off[u]  element offset of vector u inside its image, res_base: the image's first element (residual operands)
-// CODE >= 0: the kinds of the list's operations are known at compile time (one base-K_EW_BASE digit per operation, the first
-// in the lowest digit; n_ew is ignored) and the list unrolls into straight code; arguments still come from `ew`.
-constexpr int tile_code_len(int code)
-{
-    int n = 0;
-    while (code > 0) {
-        ++n;
-        code /= K_EW_BASE;
-    }
-    return n;
-}
-constexpr int tile_code_kind(int code, int q)
-{
-    for (int i = 0; i < q; ++i) code /= K_EW_BASE;
-    return code % K_EW_BASE;
-}
+// CODE >= 0: the kinds of the list's operations are known at compile time (a code of base-K_EW_BASE digits; n_ew is
+// ignored) and the list unrolls into straight code; arguments still come from `ew`.
 
 template <int DT, int VEC, int U, int CODE = -1>
 BS_DEV void apply_ew_tile(float (&x)[U][VEC], const uint32_t (&off)[U], const EwOp *ew, int32_t n_ew, const float *par, uint32_t stride,
@@ -234,7 +220,7 @@ BS_DEV void apply_ew_tile(float (&x)[U][VEC], const uint32_t (&off)[U], const Ew
     };
     if constexpr (CODE >= 0) {
 #pragma unroll
-        for (int j = 0; j < tile_code_len(CODE); ++j) one(tile_code_kind(CODE, j), ew[j].arg);
+        for (int j = 0; j < ew_code_len(CODE); ++j) one(ew_code_kind(CODE, j), ew[j].arg);
     } else {
 #pragma clang loop unroll(disable)
         for (int32_t j = 0; j < n_ew; ++j) one(ew[j].kind, ew[j].arg);
@@ -318,7 +304,7 @@ BS_DEV void pool_level(const NhwcTile2K &k, const PoolK &p, const LaneBlock &lb,
     // their pixels in the destination plane (clamped to it: safe addresses for the residual operands of cells outside)
     uint32_t pixel[NB], off[NB];
     const uint32_t img_off = img * (uint32_t)(Hd * Wd) * (uint32_t)k.C;  // the image's first element in a dense tensor
-    const bool has_list = CODE >= 0 ? tile_code_len(CODE) > 0 : n_ew > 0;
+    const bool has_list = CODE >= 0 ? ew_code_len(CODE) > 0 : n_ew > 0;
     if (has_list || !TO_LDS) {
 #pragma unroll
         for (int o = 0; o < NB; ++o) {
@@ -482,7 +468,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(tile_waves(
                 unpack<DT, VEC>(raw[u], x[u]);
                 off[u] = mad24(pixel[u], (uint32_t)k.C, c0);
             }
-            if (SIG::PRE >= 0 ? tile_code_len(SIG::PRE) > 0 : k.n_pre > 0)
+            if (SIG::PRE >= 0 ? ew_code_len(SIG::PRE) > 0 : k.n_pre > 0)
                 apply_ew_tile<DT, VEC, U, SIG::PRE>(x, off, k.pre, k.n_pre, par_lane, par_stride, k.params, k.res,
                                                     tp.n * (uint32_t)(k.H * k.W) * (uint32_t)k.C);
 #pragma unroll

@@ -17,19 +17,8 @@ constexpr int RW_BN_RELU = OP_BN + K_EW_BASE * OP_RELU;
 
 template <int CODE>
 struct RowsEw {
-    static constexpr int count()
-    {
-        int n = 0, c = CODE;
-        while (c) { ++n; c /= K_EW_BASE; }
-        return n;
-    }
-    static constexpr int n = count();
-    __host__ __device__ static constexpr int kind(int j)
-    {
-        int c = CODE;
-        for (int i = 0; i < j; ++i) c /= K_EW_BASE;
-        return c % K_EW_BASE;
-    }
+    static constexpr int n = ew_code_len(CODE);
+    __host__ __device__ static constexpr int kind(int j) { return ew_code_kind(CODE, j); }
 };
 
 template <class EW>
