@@ -44,6 +44,22 @@ BS_DEV uint32_t xcd_contiguous(uint32_t bid, uint32_t n)
 // by the compiler's conversions (v_cvt_pk_bf16_f32 / v_cvt_f16_f32).
 constexpr int DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2;
 
+// Two float32 values rounded to the 16-bit storage type, in one 32-bit word (a in the low half).  bfloat16: one
+// v_cvt_pk_bf16_f32.
+template <int DT>
+BS_DEV uint32_t pack2(float a, float b)
+{
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const f2 v = {a, b};
+    if constexpr (DT == DT_BF16) {
+        typedef __bf16 h2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, h2));
+    } else {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, h2));
+    }
+}
+
 template <int DT>
 BS_DEV uint16_t half_bits(float f)
 {
@@ -77,6 +93,25 @@ BS_DEV float round_store(float v)
         return (float)(_Float16)v;
     } else {
         return v;
+    }
+}
+
+// round_store on N values at once.  bfloat16: pairs share one v_cvt_pk_bf16_f32 (three instructions per two values
+// instead of four, and no conversion with an unused second operand, which the compiler fills with whatever register is
+// at hand -- the target of a load in flight makes the conversion wait for that load).
+template <int DT, int N>
+BS_DEV void round_store_all(float (&x)[N])
+{
+    if constexpr (DT == DT_BF16 && N % 2 == 0) {
+#pragma unroll
+        for (int i = 0; i < N; i += 2) {
+            const uint32_t w = pack2<DT_BF16>(x[i], x[i + 1]);
+            x[i] = __uint_as_float(w << 16);
+            x[i + 1] = __uint_as_float(w & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) x[i] = round_store<DT>(x[i]);
     }
 }
 
@@ -223,7 +258,7 @@ BS_DEV void store_elems(void *base, uint32_t elem, const float (&v)[N])
             uint32_t w[N / 2];
 #pragma unroll
             for (int i = 0; i < N / 2; ++i)
-                w[i] = (uint32_t)half_bits<DT>(v[2 * i]) | ((uint32_t)half_bits<DT>(v[2 * i + 1]) << 16);
+                w[i] = pack2<DT>(v[2 * i], v[2 * i + 1]);
             if constexpr (N == 8) {
                 const u4 t = {w[0], w[1], w[2], w[3]};
                 if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<u4 *>(p));

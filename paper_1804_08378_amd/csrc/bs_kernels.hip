@@ -53,9 +53,11 @@ BS_DEV void apply_ew(float (&x)[U][VEC], const int32_t (&c)[U], const uint32_t (
                 sh[u] = params[arg + C + c[u]];
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(__builtin_fmaf(x[u][i], sc[u], sh[u]));
+                for (int i = 0; i < VEC; ++i) x[u][i] = __builtin_fmaf(x[u][i], sc[u], sh[u]);
+                round_store_all<DT, VEC>(x[u]);
+            }
         } else if (kind == OP_RELU) {
 #pragma unroll
             for (int u = 0; u < U; ++u)

@@ -38,9 +38,11 @@ BS_DEV void apply_ew_nhwc(float (&x)[U][VEC], uint32_t c0, const uint32_t (&off)
             load_params<VEC>(params, (uint32_t)arg + c0, sc);
             load_params<VEC>(params, (uint32_t)(arg + C) + c0, sh);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(__builtin_fmaf(x[u][i], sc[i], sh[i]));
+                for (int i = 0; i < VEC; ++i) x[u][i] = __builtin_fmaf(x[u][i], sc[i], sh[i]);
+                round_store_all<DT, VEC>(x[u]);
+            }
         } else if (kind == OP_RELU) {
 #pragma unroll
             for (int u = 0; u < U; ++u)

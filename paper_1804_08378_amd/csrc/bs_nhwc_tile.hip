@@ -184,9 +184,11 @@ BS_DEV void apply_ew_tile(float (&x)[U][VEC], const uint32_t (&off)[U], const Ew
             }
             par += 2 * stride;
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) x[u][i] = round_store<DT>(__builtin_fmaf(x[u][i], sc[i], sh[i]));
+                for (int i = 0; i < VEC; ++i) x[u][i] = __builtin_fmaf(x[u][i], sc[i], sh[i]);
+                round_store_all<DT, VEC>(x[u]);
+            }
         } else if (kind == OP_RELU) {
 #pragma unroll
             for (int u = 0; u < U; ++u)

@@ -52,7 +52,8 @@ BS_DEV void rows_apply(float (&x)[N], const RowsParams<EW> &p)
     for (int j = 0; j < EW::n; ++j) {
         if (EW::kind(j) == OP_BN) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) x[i] = round_store<DT>(__builtin_fmaf(x[i], p.sc[j], p.sh[j]));
+            for (int i = 0; i < N; ++i) x[i] = __builtin_fmaf(x[i], p.sc[j], p.sh[j]);
+            round_store_all<DT, N>(x);
         } else if (EW::kind(j) == OP_LEAKY) {
 #pragma unroll
             for (int i = 0; i < N; ++i) x[i] = round_store<DT>(x[i] > 0.0f ? x[i] : x[i] * p.sc[j]);

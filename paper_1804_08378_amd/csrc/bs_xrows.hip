@@ -55,11 +55,22 @@ std::string xrows_expr(const PoolRowsK &k, int32_t dtype, bool want_idx)
            spec_expr(k.pool) + b;
 }
 
+// The conditions pool_xrows2_kernel's PLAIN instances take for granted.
+bool xrows2_is_plain(const PoolRows2K &k, int32_t dtype)
+{
+    const int32_t vec = xrows2_vec(dtype);
+    if (k.pool1.sw < 1 || k.pool2.sw < 1 || vec % (k.pool1.sw * k.pool2.sw) != 0) return false;
+    const int32_t vb = vec / k.pool1.sw, vo = vb / k.pool2.sw;
+    const bool divisors = (k.pool1.kind == OP_MAXPOOL || k.pool1.count_include_pad == 1) &&
+                          (k.pool2.kind == OP_MAXPOOL || k.pool2.count_include_pad == 1);
+    return divisors && k.W1 >= k.cbs * vb && k.Wo % vo == 0 && k.cbs * vo <= k.Wo;
+}
+
 std::string xrows2_expr(const PoolRows2K &k, int32_t dtype, bool want_idx)
 {
     char b[96];
-    std::snprintf(b, sizeof b, ", %d, %d, %d, %s>", rows_ew_code(k.pre, k.n_pre), rows_ew_code(k.mid, k.n_mid),
-                  rows_ew_code(k.post, k.n_post), want_idx ? "true" : "false");
+    std::snprintf(b, sizeof b, ", %d, %d, %d, %s, %s>", rows_ew_code(k.pre, k.n_pre), rows_ew_code(k.mid, k.n_mid),
+                  rows_ew_code(k.post, k.n_post), want_idx ? "true" : "false", xrows2_is_plain(k, dtype) ? "true" : "false");
     return std::string("bs::pool_xrows2_kernel<") + std::to_string(dtype) + ", " + std::to_string(xrows2_vec(dtype)) + ", " +
            spec_expr(k.pool1) + ", " + spec_expr(k.pool2) + b;
 }
@@ -122,8 +133,11 @@ static bool xrows2_launch_t(const PoolRows2K &k, bool want_idx, dim3 grid, dim3 
         using P2 = decltype(s2);
         constexpr int C0 = decltype(e0)::value, C1 = decltype(e1)::value, C2 = decltype(e2)::value;
         if (!rows_pool_is<P1>(k.pool1) || !rows_pool_is<P2>(k.pool2) || c0 != C0 || c1 != C1 || c2 != C2) return false;
-        if (want_idx) pool_xrows2_kernel<DT, VEC, P1, P2, C0, C1, C2, true><<<grid, block, 0, st>>>(k);
-        else pool_xrows2_kernel<DT, VEC, P1, P2, C0, C1, C2, false><<<grid, block, 0, st>>>(k);
+        const bool plain = xrows2_is_plain(k, DT == DT_BF16 ? BS_BF16 : BS_F32);
+        if (want_idx && plain) pool_xrows2_kernel<DT, VEC, P1, P2, C0, C1, C2, true, true><<<grid, block, 0, st>>>(k);
+        else if (want_idx) pool_xrows2_kernel<DT, VEC, P1, P2, C0, C1, C2, true, false><<<grid, block, 0, st>>>(k);
+        else if (plain) pool_xrows2_kernel<DT, VEC, P1, P2, C0, C1, C2, false, true><<<grid, block, 0, st>>>(k);
+        else pool_xrows2_kernel<DT, VEC, P1, P2, C0, C1, C2, false, false><<<grid, block, 0, st>>>(k);
         return true;
     });
 }

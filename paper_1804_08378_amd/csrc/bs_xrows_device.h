@@ -40,9 +40,6 @@
 
 namespace bs {
 
-#if !defined(BS_XROWS2_UNROLL)
-#define BS_XROWS2_UNROLL 1
-#endif
 // value of the same register in lane - 1 / lane + 1 of the wave (lane 0 / lane 63: zero bits)
 BS_DEV float from_left_lane(float v)
 {
@@ -128,6 +125,18 @@ BS_DEV void xrows_unpack(const XRowRaw<DT, VEC> &r, float (&x)[VEC])
         unpack<DT, R::VPC>(r.v[p], xv);
 #pragma unroll
         for (int n = 0; n < R::VPC; ++n) x[p * R::VPC + n] = xv[n];
+    }
+}
+
+// bfloat16 storage, index-producing scans: the rounded values of a settled row are used by every window that holds
+// them.  Left to itself the compiler repeats the conversions at the uses; a value the optimiser cannot look into is
+// converted once (measured on the ResNet stem with indices: 51 -> 42 us; binary16 gains nothing from it).
+template <int DT, bool WANT_IDX, int N>
+BS_DEV void xrows_pin(float (&x)[N])
+{
+    if constexpr (WANT_IDX && DT == DT_BF16) {
+#pragma unroll
+        for (int n = 0; n < N; ++n) asm("" : "+v"(x[n]));
     }
 }
 
@@ -297,6 +306,7 @@ __global__ __launch_bounds__(256) void pool_xrows_kernel(const PoolRowsK k)
         float x[VEC];
         xrows_unpack<DT, VEC>(r, x);
         xrows_apply<DT, EWP, VEC, DEFER>(x, pp);
+        xrows_pin<DT, WANT_IDX>(x);
         const bool ok = ih >= 0 && ih < k.H;
 #pragma unroll
         for (int n = 0; n < VEC; ++n) x[n] = ok ? x[n] : padv;
@@ -405,8 +415,11 @@ __global__ __launch_bounds__(256) void pool_xrows_kernel(const PoolRowsK k)
 // level-0 rows (input after the leading element-wise operations) and the kh2 level-1 rows
 // (first pool's output after the middle operations) under the current output row; per output
 // row it loads sh1 * sh2 new input rows and produces sh2 level-1 rows and one output row.
+// PLAIN: the launcher has checked that every average divides by kh * kw, that no lane's level-1 columns reach
+// past the plane and that every lane's outputs of a row are one aligned vector (xrows2_is_plain): the tests of
+// these conditions, the same for all lanes and rows, are then not in the loop.
 // =============================================================================
-template <int DT, int VEC, class P1, class P2, int EW0, int EW1, int EW2, bool WANT_IDX>
+template <int DT, int VEC, class P1, class P2, int EW0, int EW1, int EW2, bool WANT_IDX, bool PLAIN = false>
 __global__ __launch_bounds__(256) void pool_xrows2_kernel(const PoolRows2K k)
 {
     constexpr int KH1 = P1::kh, KW1 = P1::kw, SH1 = P1::sh, SW1 = P1::sw, PH1 = P1::ph, PW1 = P1::pw;
@@ -436,9 +449,6 @@ __global__ __launch_bounds__(256) void pool_xrows2_kernel(const PoolRows2K k)
     // middle list, else of an average as first pool -- moves behind it
     constexpr bool DEFER_E1 = VF2 && DT != DT_F32 && has_rounding<E1>();
     constexpr bool DEFER_AVG = VF2 && DT != DT_F32 && !has_rounding<E1>() && !MAX1;
-    // Output rows per pass of the loop body: after that many rows the sliding windows are back
-    // in the registers they started in, so most of the moves that slide them disappear.
-    constexpr int UNROLL = 2;
     const float pad0 = MAX1 ? -INFINITY : 0.0f;  // value of a cell outside the level-0 plane
     const float pad1 = MAX2 ? -INFINITY : 0.0f;  // value of a cell outside the level-1 plane
 
@@ -456,13 +466,14 @@ __global__ __launch_bounds__(256) void pool_xrows2_kernel(const PoolRows2K k)
     const int32_t col0 = L.j * VEC;  // first level-0 column of the lane
     const int32_t c10 = L.j * VB;    // first level-1 column of the lane
     const bool has_left = L.j > 0, has_right = L.j + 1 < k.cbs;
-    const bool ragged1 = k.W1 < k.cbs * VB;  // the last lane's level-1 columns reach past the plane
+    const bool ragged1 = !PLAIN && k.W1 < k.cbs * VB;  // the last lane's level-1 columns reach past the plane
 
     // registers -> level-0 row: leading element-wise operations, the first pool's padding
     auto settle = [&](const Row &r, int32_t ih, float (&w)[C0]) {
         float x[VEC];
         xrows_unpack<DT, VEC>(r, x);
         rows_apply<DT, E0, VEC>(x, p0);
+        xrows_pin<DT, WANT_IDX>(x);
         const bool ok = ih >= 0 && ih < k.H;
 #pragma unroll
         for (int n = 0; n < VEC; ++n) x[n] = ok ? x[n] : pad0;
@@ -496,7 +507,12 @@ __global__ __launch_bounds__(256) void pool_xrows2_kernel(const PoolRows2K k)
         } else {
 #pragma unroll
             for (int n = 0; n < VB; ++n) v[n] = xrows_window_sum<KH1, KW1, NONNEG0, C0>(w0, n * SW1);
-            xrows_normalise<DT, VB, KH1, KW1, SW1, PH1, PW1, !DEFER_AVG>(v, k.pool1, r1 * SH1 - PH1, col0 - PW1, k.H, k.W);
+            if constexpr (PLAIN) {
+#pragma unroll
+                for (int n = 0; n < VB; ++n) v[n] = DEFER_AVG ? v[n] * k.pool1.inv_kk : round_store<DT>(v[n] * k.pool1.inv_kk);
+            } else {
+                xrows_normalise<DT, VB, KH1, KW1, SW1, PH1, PW1, !DEFER_AVG>(v, k.pool1, r1 * SH1 - PH1, col0 - PW1, k.H, k.W);
+            }
         }
         xrows_apply<DT, E1, VB, DEFER_E1>(v, p1);
         const bool rok = r1 >= 0 && r1 < k.H1;
@@ -516,11 +532,9 @@ __global__ __launch_bounds__(256) void pool_xrows2_kernel(const PoolRows2K k)
 
     const int32_t oh0 = L.chunk * k.rc;
     const int32_t ow0 = L.j * VO;
-    const bool all_vec = (k.Wo % VO) == 0 && k.cbs * VO <= k.Wo;
+    const bool all_vec = PLAIN || ((k.Wo % VO) == 0 && k.cbs * VO <= k.Wo);
     const uint32_t oplane = L.plane * (uint32_t)(k.Ho * k.Wo);
 
-    // The NS0 input rows the next output row adds are requested before this row is reduced, and
-    // settled after.
     auto new_l1 = [&](int32_t t) { return (oh0 + t - 1) * SH2 - PH2 + KH2; };    // first level-1 row output row t adds
     auto new_l0 = [&](int32_t t) { return (new_l1(t) - 1) * SH1 - PH1 + KH1; };  // first level-0 row it adds
     float keep0[KEEP0 > 0 ? KEEP0 : 1][C0];  // newest level-0 rows, shared with the next level-1 row
@@ -541,91 +555,118 @@ __global__ __launch_bounds__(256) void pool_xrows2_kernel(const PoolRows2K k)
 #pragma unroll
             for (int n = 0; n < C0; ++n) keep0[w][n] = l0[R0 - KEEP0 + w][n];
     }
-    for (int32_t t0 = 0; t0 < k.rc; t0 += UNROLL) {
+    // output row t of the chunk from the level-1 rows under it
+    auto reduce = [&](int32_t t, float (&y)[VO], int32_t (&yi)[VO]) {
+        const int32_t r1w = (oh0 + t) * SH2 - PH2;  // first level-1 row of this output row's windows
+        if constexpr (VF2) {
+            float m[VB], full[NL1 + VB + NX1];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int32_t t = t0 + u;
-            if (t >= k.rc) break;  // the same for every lane
-            const int32_t oh = oh0 + t;
-            const int32_t r1w = oh * SH2 - PH2;  // first level-1 row of this output row's windows
-            const bool more = t + 1 < k.rc;      // the same for every lane
-            Row nr[NS0];
-            if (more) {
-                const int32_t h0n = new_l0(t + 1);
+            for (int n = 0; n < VB; ++n) {
+                m[n] = win1[0][n];
 #pragma unroll
-                for (int n = 0; n < NS0; ++n) xrows_fetch<DT, VEC>(inp, h0n + n, k.H, k.W, col0, nr[n]);
+                for (int dh = 1; dh < KH2; ++dh) m[n] = __builtin_fmaxf(m[n], win1[dh][n]);
             }
-
-            float y[VO];
-            int32_t yi[VO];
-            if constexpr (VF2) {
-                float m[VB], full[NL1 + VB + NX1];
+            with_neighbours<VB, NL1, NX1>(m, full, has_left, has_right, pad1);
 #pragma unroll
-                for (int n = 0; n < VB; ++n) {
-                    m[n] = win1[0][n];
+            for (int e = 0; e < VO; ++e) {
+                float best = full[e * SW2];
 #pragma unroll
-                    for (int dh = 1; dh < KH2; ++dh) m[n] = __builtin_fmaxf(m[n], win1[dh][n]);
-                }
-                with_neighbours<VB, NL1, NX1>(m, full, has_left, has_right, pad1);
+                for (int dw = 1; dw < KW2; ++dw) best = __builtin_fmaxf(best, full[e * SW2 + dw]);
+                y[e] = (DEFER_E1 || DEFER_AVG) ? round_store<DT>(best) : best;
+                yi[e] = 0;
+            }
+        } else if constexpr (MAX2) {
 #pragma unroll
-                for (int e = 0; e < VO; ++e) {
-                    float best = full[e * SW2];
+            for (int e = 0; e < VO; ++e) {
+                const int32_t w0 = c10 - PW2 + e * SW2;  // first level-1 column of this output's window
+                float best = -INFINITY;
+                int32_t bi = max(r1w, 0) * k.W1 + max(w0, 0);  // first in-range cell
 #pragma unroll
-                    for (int dw = 1; dw < KW2; ++dw) best = __builtin_fmaxf(best, full[e * SW2 + dw]);
-                    y[e] = (DEFER_E1 || DEFER_AVG) ? round_store<DT>(best) : best;
-                    yi[e] = 0;
-                }
-            } else if constexpr (MAX2) {
+                for (int dh = 0; dh < KH2; ++dh)
 #pragma unroll
-                for (int e = 0; e < VO; ++e) {
-                    const int32_t w0 = c10 - PW2 + e * SW2;  // first level-1 column of this output's window
-                    float best = -INFINITY;
-                    int32_t bi = max(r1w, 0) * k.W1 + max(w0, 0);  // first in-range cell
+                    for (int dw = 0; dw < KW2; ++dw) {
+                        const float v = win1[dh][e * SW2 + dw];
+                        const bool g = v > best;
+                        best = g ? v : best;
+                        bi = g ? (r1w + dh) * k.W1 + w0 + dw : bi;
+                    }
+                y[e] = best;
+                yi[e] = bi;
+            }
+        } else {
 #pragma unroll
-                    for (int dh = 0; dh < KH2; ++dh)
+            for (int e = 0; e < VO; ++e) {
+                y[e] = xrows_window_sum<KH2, KW2, NONNEG1, C1>(win1, e * SW2);
+                yi[e] = 0;
+            }
+            if constexpr (PLAIN) {
 #pragma unroll
-                        for (int dw = 0; dw < KW2; ++dw) {
-                            const float v = win1[dh][e * SW2 + dw];
-                            const bool g = v > best;
-                            best = g ? v : best;
-                            bi = g ? (r1w + dh) * k.W1 + w0 + dw : bi;
-                        }
-                    y[e] = best;
-                    yi[e] = bi;
-                }
+                for (int e = 0; e < VO; ++e) y[e] = round_store<DT>(y[e] * k.pool2.inv_kk);
             } else {
-#pragma unroll
-                for (int e = 0; e < VO; ++e) {
-                    y[e] = xrows_window_sum<KH2, KW2, NONNEG1, C1>(win1, e * SW2);
-                    yi[e] = 0;
-                }
                 xrows_normalise<DT, VO, KH2, KW2, SW2, PH2, PW2>(y, k.pool2, r1w, c10 - PW2, k.H1, k.W1);
             }
-            rows_apply<DT, E2, VO>(y, p2);
-            xrows_store<DT, VO, WANT_IDX, false>(outp, k.idx, oplane + (uint32_t)(oh * k.Wo + ow0), y, yi, all_vec, ow0, k.Wo,
-                                          L.live && oh < k.Ho);
-            // slide both windows down to the next output row
-#pragma unroll
-            for (int w = 0; w < KEEP1; ++w)
-#pragma unroll
-                for (int n = 0; n < C1; ++n) win1[w][n] = win1[w + SH2][n];
-            if (more) {
-                const int32_t r1n = new_l1(t + 1), h0n = new_l0(t + 1);
-                float l0[KEEP0 + NS0][C0];
-#pragma unroll
-                for (int w = 0; w < KEEP0; ++w)
-#pragma unroll
-                    for (int n = 0; n < C0; ++n) l0[w][n] = keep0[w][n];
-#pragma unroll
-                for (int n = 0; n < NS0; ++n) settle(nr[n], h0n + n, l0[KEEP0 + n]);
-#pragma unroll
-                for (int a = 0; a < SH2; ++a) level1(r1n + a, &l0[a * SH1], win1[KEEP1 + a]);
-#pragma unroll
-                for (int w = 0; w < KEEP0; ++w)
-#pragma unroll
-                    for (int n = 0; n < C0; ++n) keep0[w][n] = l0[NS0 + w][n];
-            }
         }
+        rows_apply<DT, E2, VO>(y, p2);
+    };
+    auto put = [&](int32_t t, const float (&y)[VO], const int32_t (&yi)[VO]) {
+        const int32_t oh = oh0 + t;
+        xrows_store<DT, VO, WANT_IDX, false>(outp, k.idx, oplane + (uint32_t)(oh * k.Wo + ow0), y, yi, all_vec, ow0, k.Wo,
+                                             L.live && oh < k.Ho);
+    };
+    // One output row, and both windows slid down to the next: the NS0 input rows the next row adds are requested
+    // before this row is reduced and settled after; the row's store comes last, so that the wait for the requested
+    // rows has only a store issued a whole row earlier in front of them.
+    auto step = [&](int32_t t) {
+        Row nr[NS0];
+        const int32_t r1n = new_l1(t + 1), h0n = new_l0(t + 1);
+#pragma unroll
+        for (int n = 0; n < NS0; ++n) xrows_fetch<DT, VEC>(inp, h0n + n, k.H, k.W, col0, nr[n]);
+        float y[VO];
+        int32_t yi[VO];
+        reduce(t, y, yi);
+#pragma unroll
+        for (int w = 0; w < KEEP1; ++w)
+#pragma unroll
+            for (int n = 0; n < C1; ++n) win1[w][n] = win1[w + SH2][n];
+        float l0[KEEP0 + NS0][C0];
+#pragma unroll
+        for (int w = 0; w < KEEP0; ++w)
+#pragma unroll
+            for (int n = 0; n < C0; ++n) l0[w][n] = keep0[w][n];
+#pragma unroll
+        for (int n = 0; n < NS0; ++n) settle(nr[n], h0n + n, l0[KEEP0 + n]);
+#pragma unroll
+        for (int a = 0; a < SH2; ++a) level1(r1n + a, &l0[a * SH1], win1[KEEP1 + a]);
+#pragma unroll
+        for (int w = 0; w < KEEP0; ++w)
+#pragma unroll
+            for (int n = 0; n < C0; ++n) keep0[w][n] = l0[NS0 + w][n];
+        put(t, y, yi);
+    };
+    auto last = [&](int32_t t) {
+        float y[VO];
+        int32_t yi[VO];
+        reduce(t, y, yi);
+        put(t, y, yi);
+    };
+    // The compiler places the waits for loads by what may be in flight on *any* path to a use, so the loop leaves
+    // it no doubt.  Nothing is in flight when the loop starts: a load whose first use lies inside the loop (the
+    // trailing list's parameters) would make it wait for all loads at that use, in every iteration -- the rows just
+    // requested included.  Every pass through the loop body requests rows and uses them, with no condition on
+    // either (the chunk's last row, which requests nothing, stands behind the loop): a request skipped on one path
+    // and a use skipped on another would look like a request that may still be open where the next ones are issued.
+    // Two rows per pass: after two rows the sliding windows are back in the registers they started in.
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+    int32_t t = 0;
+    for (; t + 2 < k.rc; t += 2) {  // the same for every lane
+        step(t);
+        step(t + 1);
+    }
+    if (t + 2 == k.rc) {
+        step(t);
+        last(t + 1);
+    } else {
+        last(t);
     }
 }
 
