@@ -67,11 +67,26 @@ BS_DEV float bwd_avg_inv(const PoolK &p, int32_t H, int32_t W, int32_t oh, int32
 // The list is k.ew[first .. first + count).
 // CODE >= 0: the kinds of the list's operations are known at compile time (a code of base-K_EW_BASE digits; `count` is
 // ignored) and the loop over the list unrolls into straight code; their arguments still come from k.ew.
+// cache (CODE >= 0, row-major, not FLAT, all rows in one channel): scale and shift of the list's q-th operation at
+// cache[2 * q], cache[2 * q + 1], read once by ew_load_cache.  A kernel that calls this in a loop and stores between the
+// calls would otherwise read the parameters again in every iteration (the compiler cannot know that the stores leave
+// them alone) and wait for them, with everything else it has in flight.
+template <int CODE>
+BS_DEV void ew_load_cache(const BwdK &k, int32_t c, int32_t first, float (&cache)[2 * (ew_code_len(CODE) > 0 ? ew_code_len(CODE) : 1)])
+{
+#pragma unroll
+    for (int q = 0; q < ew_code_len(CODE); ++q)
+        if (ew_code_kind(CODE, q) == OP_BN) {
+            const int32_t arg = k.ew[first + q].arg;
+            cache[2 * q] = k.params[arg + c];
+            cache[2 * q + 1] = k.params[arg + k.C + c];
+        }
+}
 
 template <int DT, int VEC, int R, bool CL, int NR, bool FLAT, int CODE = -1>
 BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_t (&off)[R], float (&x)[R][VEC],
                              float (&t)[R][VEC], float (&r)[NR ? NR : 1][R][VEC], const uint32_t (&nfirst)[R], int32_t first,
-                             int32_t count)
+                             int32_t count, const float *cache = nullptr)
 {
 #pragma unroll
     for (int j = 0; j < R; ++j)
@@ -82,7 +97,7 @@ BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_
             for (int n = 0; n < NR; ++n) r[n][j][e] = 0.0f;
         }
     int32_t adds = 0;
-    auto one = [&](const int32_t kind, const int32_t arg) {
+    auto one = [&](const int32_t kind, const int32_t arg, const int q) {
         if (kind == OP_ADD) {
             if constexpr (NR == 0) return;  // instances for stages without Add (chosen at launch): nothing to read
             Raw<DT, VEC> raw[R];
@@ -138,8 +153,13 @@ BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_
                 float sc[R], sh[R], sc1[R], sh1[R];
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
-                    sc[j] = k.params[arg + c[j]];
-                    sh[j] = k.params[arg + k.C + c[j]];
+                    if (CODE >= 0 && !FLAT && cache) {
+                        sc[j] = cache[2 * q];
+                        sh[j] = cache[2 * q + 1];
+                    } else {
+                        sc[j] = k.params[arg + c[j]];
+                        sh[j] = k.params[arg + k.C + c[j]];
+                    }
                     if constexpr (FLAT) {
                         const int32_t cn = c[j] + 1 == k.C ? 0 : c[j] + 1;
                         sc1[j] = k.params[arg + cn];
@@ -196,10 +216,10 @@ BS_DEV int32_t ew_sweep_impl(const BwdK &k, const int32_t (&c)[R], const uint32_
     };
     if constexpr (CODE >= 0) {
 #pragma unroll
-        for (int q = 0; q < ew_code_len(CODE); ++q) one(ew_code_kind(CODE, q), k.ew[first + q].arg);
+        for (int q = 0; q < ew_code_len(CODE); ++q) one(ew_code_kind(CODE, q), k.ew[first + q].arg, q);
     } else {
 #pragma clang loop unroll(disable)
-        for (int32_t q = first; q < first + count; ++q) one(k.ew[q].kind, k.ew[q].arg);
+        for (int32_t q = first; q < first + count; ++q) one(k.ew[q].kind, k.ew[q].arg, 0);
     }
     return adds;
 }
@@ -773,6 +793,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BS_ROWS2_WA
 
     float yf[4][YW], T[5][VEC], af[3][AW], gt[3][VEC], hs[4][VEC];
     const int32_t cs1[1] = {L.c};
+    // both lists' BatchNorm parameters of the lane's channel
+    float pre_par[2 * (ew_code_len(PRE) > 0 ? ew_code_len(PRE) : 1)], post_par[2 * (ew_code_len(POST) > 0 ? ew_code_len(POST) : 1)];
+    if constexpr (PRE >= 0) ew_load_cache<PRE>(k, L.c, 0, pre_par);
+    if constexpr (POST >= 0) ew_load_cache<POST>(k, L.c, k.n_ew, post_par);
 
     // rows [first, first + N) of the plane: leading element-wise list -> y with edge columns (padding +0: the
     // average's) into yf[slot ..], derivative factors into T[tslot ..]
@@ -791,7 +815,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BS_ROWS2_WA
 #pragma unroll
         for (int j = 0; j < N; ++j) unpack<DT, VEC>(raw[j], xs[j]);
         const uint32_t whole[N] = {};
-        ew_sweep_impl<DT, VEC, N, false, 0, false, PRE>(k, cs, offs, xs, ts, none, whole, 0, k.n_ew);
+        ew_sweep_impl<DT, VEC, N, false, 0, false, PRE>(k, cs, offs, xs, ts, none, whole, 0, k.n_ew, PRE >= 0 ? pre_par : nullptr);
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const bool ok = first + j >= 0 && first + j < k.H;
@@ -867,7 +891,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BS_ROWS2_WA
             const uint32_t no_off[1] = {0}, all[1] = {VO};
 #pragma unroll
             for (int e = 0; e < VO; ++e) best[0][e] = row_ok ? best[0][e] : 0.0f;  // windows that do not exist: any finite value
-            ew_sweep_impl<DT, VO, 1, false, 0, false, POST>(k, cs1, no_off, best, tp, none, all, k.n_ew, k.n_post);
+            ew_sweep_impl<DT, VO, 1, false, 0, false, POST>(k, cs1, no_off, best, tp, none, all, k.n_ew, k.n_post,
+                                                            POST >= 0 ? post_par : nullptr);
 #pragma unroll
             for (int e = 0; e < VO; ++e) g[e] *= tp[0][e];
         }
