@@ -465,10 +465,18 @@ static bs_status launch_nhwc_t(const NhwcK &k, int32_t dtype, dim3 grid, dim3 bl
     if (p.kind == 0) {
         // the lists of the common networks compiled in: BatchNorm, ReLU (DenseNet) and BatchNorm, Add, ReLU (ResNet)
         constexpr int BN_RELU = OP_BN + OP_RELU * K_EW_BASE, BN_ADD_RELU = OP_BN + (OP_ADD + OP_RELU * K_EW_BASE) * K_EW_BASE;
-        const int32_t code = VEC > 1 ? list_code(k.pre, k.n_pre) : -1;
-        if (code == BN_RELU) nhwc_stream_kernel<DT, VEC, K_STREAM_U, BN_RELU><<<grid, block, 0, st>>>(k);
-        else if (code == BN_ADD_RELU) nhwc_stream_kernel<DT, VEC, K_STREAM_U, BN_ADD_RELU><<<grid, block, 0, st>>>(k);
-        else nhwc_stream_kernel<DT, VEC, K_STREAM_U><<<grid, block, 0, st>>>(k);
+        if constexpr (VEC > 1) {
+            const int32_t code = list_code(k.pre, k.n_pre);
+            if (code == BN_RELU) {
+                nhwc_stream_kernel<DT, VEC, K_STREAM_U, BN_RELU><<<grid, block, 0, st>>>(k);
+                return BS_OK;
+            }
+            if (code == BN_ADD_RELU) {
+                nhwc_stream_kernel<DT, VEC, K_STREAM_U, BN_ADD_RELU><<<grid, block, 0, st>>>(k);
+                return BS_OK;
+            }
+        }
+        nhwc_stream_kernel<DT, VEC, K_STREAM_U><<<grid, block, 0, st>>>(k);
         return BS_OK;
     }
     if (k.cv_group > 0) {
