@@ -61,7 +61,12 @@ constexpr int K_MAX_STREAM_EW = 16;
 constexpr int K_MAX_RES = 4;      // residual tensors one sequence can read
 constexpr int K_MAX_IDX = 4;      // index tensors one sequence can write
 constexpr int K_STREAM_U = 2;     // 128-bit vectors per lane in stream_kernel (measured on MI355X: 1 is 3..9 points of HBM peak slower, 4 is 1..3 slower with 16-bit storage)
-constexpr int K_ROWS_OR = 2;     // output rows per lane per iteration of the one-level sliding-window kernels (all their input rows are requested at once)
+#if !defined(BS_ROWS_OR)
+#define BS_ROWS_OR 2
+#endif
+// Measured on MI355X (ResNet stem, float32 / bfloat16 / with indices float32, us): 2 rows 46.1 / 27.5 / 64.8, 3 rows 46.5 / 29.2 / 64.7,
+// 4 rows 46.8 / 29.2 / 62.6.
+constexpr int K_ROWS_OR = BS_ROWS_OR;     // output rows per lane per iteration of the one-level sliding-window kernels (all their input rows are requested at once)
 constexpr int K_ROWS2_RC = 4;    // output rows per lane in pool_rows2_kernel
 // Elements per lane and row (the lane's column block) of the sliding-window kernels for 16-bit
 // storage: one 128-bit load, as for float32 (4).  Measured on MI355X, 64-bit blocks (twice the

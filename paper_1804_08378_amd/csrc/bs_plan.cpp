@@ -1060,7 +1060,7 @@ static void plan_rows(const bs_stack *s, Sequence &q, const bs_plan_options &o, 
     // are served by the L1/L2 caches, while long chunks leave each lane a chain of dependent
     // memory round trips.  With two rows per lane (and the kernel producing two output rows per
     // iteration) a lane requests all its input rows at once: one round trip per wave.
-    int32_t rc = std::min(2, k.Ho);
+    int32_t rc = std::min(K_ROWS_OR, k.Ho);
     (void)lim;
     if (o.tile_rows > 0) rc = std::min(o.tile_rows, k.Ho);
     if (k.spw > 0) {
