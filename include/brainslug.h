@@ -138,8 +138,11 @@ typedef enum bs_variant {
     BS_VARIANT_NHWC_STREAM = 6, /* channels-last plans only: element-wise, one channel vector per lane   */
     BS_VARIANT_NHWC_POOL = 7,   /* channels-last plans only: one pooling step, a lane = one output pixel x one channel vector */
     BS_VARIANT_NHWC_TILE = 8,   /* channels-last plans only: two pooling steps, tiles of both planes with halos staged in LDS */
-    BS_VARIANT_ROWS_CHAIN = 9   /* two and more identical max-pooling steps that keep the plane's size, each with the same
+    BS_VARIANT_ROWS_CHAIN = 9,  /* two and more identical max-pooling steps that keep the plane's size, each with the same
                                    kinds of element-wise operations behind it: rows ripple through all levels in registers */
+    BS_VARIANT_NHWC_ROWS = 10   /* channels-last plans only: two 3 x 3 pooling steps (the first with stride 1, the second a
+                                   maximum) on images at most 64 pixels wide: rows slide in registers, a lane = one pixel
+                                   column x one channel vector, no LDS */
 } bs_variant;
 
 /* Memory order of every tensor of a planned stack (shapes are always given as N, C, H, W). */

@@ -21,9 +21,9 @@ BS_F32, BS_BF16, BS_F16 = 0, 1, 2
 BS_BATCHNORM, BS_RELU, BS_ADD, BS_MAXPOOL, BS_AVGPOOL, BS_LEAKY_RELU, BS_CLAMP = 1, 2, 3, 4, 5, 6, 7
 BS_VARIANT_AUTO, BS_VARIANT_STREAM, BS_VARIANT_POOL_DIRECT, BS_VARIANT_LDS_TILE = 0, 1, 2, 3
 BS_VARIANT_POOL_ROWS, BS_VARIANT_PLANE_POOL = 4, 5
-BS_VARIANT_NHWC_STREAM, BS_VARIANT_NHWC_POOL, BS_VARIANT_NHWC_TILE, BS_VARIANT_ROWS_CHAIN = 6, 7, 8, 9
+BS_VARIANT_NHWC_STREAM, BS_VARIANT_NHWC_POOL, BS_VARIANT_NHWC_TILE, BS_VARIANT_ROWS_CHAIN, BS_VARIANT_NHWC_ROWS = 6, 7, 8, 9, 10
 VARIANT_NAMES = {1: "stream", 2: "pool_direct", 3: "lds_tile", 4: "pool_rows", 5: "plane_pool", 6: "nhwc_stream",
-                 7: "nhwc_pool", 8: "nhwc_tile", 9: "rows_chain"}
+                 7: "nhwc_pool", 8: "nhwc_tile", 9: "rows_chain", 10: "nhwc_rows"}
 BS_LAYOUT_NCHW, BS_LAYOUT_NHWC = 0, 1
 STATUS_NAMES = {
     0: "BS_OK", 1: "BS_ERR_NULL", 2: "BS_ERR_SHAPE", 3: "BS_ERR_PARAM", 4: "BS_ERR_UNSUPPORTED",

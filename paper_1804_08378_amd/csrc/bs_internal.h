@@ -169,6 +169,9 @@ bs_status launch_nhwc(const NhwcK &k, int32_t dtype, int32_t vec, int64_t grid, 
                       void *stream);
 // bs_nhwc_tile.hip: channels-last, two pooling steps per sequence
 bool nhwc_tile2_supported(const PoolK &pool1, const PoolK &pool2);
+// bs_nhwc_rows.hip: the same pair of steps in registers, for the windows and lists it is compiled for
+bool nhwc_rows2_supported(const NhwcTile2K &k, int32_t dtype);
+bs_status launch_nhwc_rows2(const NhwcTile2K &k, int32_t dtype, int32_t vec, int64_t grid, int32_t threads, void *stream);
 bool nhwc_tile2_sizes_ok(int64_t H, int64_t W, int64_t C, int64_t extra_per_pixel, int32_t dtype);
 void nhwc_tile2_shape(const PoolK &p1, const PoolK &p2, int32_t th, int32_t tw, int32_t (&r0)[2], int32_t (&r1)[2], int32_t (&cells)[2],
                       int32_t (&bw)[2]);

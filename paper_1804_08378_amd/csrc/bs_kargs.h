@@ -80,6 +80,10 @@ constexpr int K_XROWS2_VEC32 = 4, K_XROWS2_VEC16 = 8;  // two pooling operations
 // Output rows per lane in pool_xrows2_kernel.  Longer chunks recompute less, but the kernel is bound by
 // instruction issue and wants many waves: measured best on 56 x 56 planes.
 constexpr int K_XROWS2_RC32 = 2, K_XROWS2_RC16 = 4;
+constexpr int K_NHWC_ROWS_WAVES = 8;  // channel vectors (waves) per work-group of nhwc_rows2_kernel: the 128 bytes of one cache line
+// Output rows per chunk of that kernel.  Measured on MI355X (halo_stress, 28 output rows, bfloat16 / binary16, us): 2 -> 89 / 65,
+// 4 -> 75 / 59, 7 -> 70 / 56, 14 -> 66 / 55.
+constexpr int K_NHWC_ROWS_RC = 14;
 constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel (2 measured 1..2 % slower on the VGG stacks)
 constexpr int K_PLANE_WALK_CELLS = 16;  // whole-plane pooling: planes up to this many cells are walked in global
@@ -280,6 +284,10 @@ struct NhwcTile2K {
     FastDiv div_cvb, div_r0w, div_n, div_tiles_w, div_tiles_h;
     FastDiv div_bw1, div_bw2;    // by the blocks per rectangle row of the two pooling levels
     uint32_t in_xp, out_xp;      // as in NhwcK
+    // nhwc_rows2_kernel (no tiles: a work-group is cvb channel vectors of a chunk of rc output rows of one image;
+    // work-groups numbered (image * chunks + chunk) * cvgs + group)
+    int32_t rc, chunks;
+    FastDiv div_cvgs, div_chunks;
 };
 
 // Backward pass of one stage: element-wise operations followed by at most one pooling

@@ -734,6 +734,17 @@ bs_status launch_sequence(const bs_stack *s, const Sequence &q, const void *in, 
         if (ls != BS_OK) return ls;
         break;
     }
+    case BS_VARIANT_NHWC_ROWS: {
+        NhwcTile2K k = q.nhwc2;
+        const uint32_t hw_in = (uint32_t)(q.in_shape[2] * q.in_shape[3]), hw_out = (uint32_t)(q.out_shape[2] * q.out_shape[3]);
+        if (in_extra % hw_in != 0 || out_extra % hw_out != 0) return BS_ERR_UNSUPPORTED;
+        k.in_xp = in_extra / hw_in;
+        k.out_xp = out_extra / hw_out;
+        k.in = in; k.out = out; k.params = s->dev_params;
+        const bs_status ls = launch_nhwc_rows2(k, dtype, q.vec, q.grid, q.threads, stream);
+        if (ls != BS_OK) return ls;
+        break;
+    }
     default:
         return BS_ERR_UNSUPPORTED;
     }

@@ -599,6 +599,34 @@ static bs_status plan_nhwc_tile2(const bs_stack *s, Sequence &q, const bs_plan_o
         commutes_with_max(s, k.mid, k.n_mid, C))
         move_behind(k.mid, k.n_mid, k.post, k.n_post);
 
+    // The register kernel where it exists for this pair (plan option lane_exchange = -1: not used).
+    // A work-group is the channel vectors that share a cache line and a chunk of output rows (tile_rows overrides its length).
+    if (o.lane_exchange >= 0 && nhwc_rows2_supported(k, s->dtype)) {
+        const int32_t cvn = C / vec;
+        int32_t cvb = std::min(cvn, K_NHWC_ROWS_WAVES);
+        while (cvn % cvb != 0) --cvb;
+        k.cvb = cvb;
+        k.cvgs = cvn / cvb;
+        k.rc = std::min(o.tile_rows > 0 ? o.tile_rows : K_NHWC_ROWS_RC, k.Ho);
+        k.chunks = (k.Ho + k.rc - 1) / k.rc;
+        const int64_t total = q.in_shape[0] * (int64_t)k.chunks * k.cvgs;
+        if (total <= 0x7fffffffll) {
+            k.div_cvgs = make_fastdiv((uint32_t)k.cvgs);
+            k.div_chunks = make_fastdiv((uint32_t)k.chunks);
+            k.div_n = make_fastdiv((uint32_t)q.in_shape[0]);
+            q.variant = BS_VARIANT_NHWC_ROWS;
+            q.threads = 64 * cvb;
+            q.grid = total;
+            q.lds_bytes = 0;
+            q.tile_rows = k.rc;
+            q.tile_cols = k.Wo;
+            q.planes_per_group = cvb * vec;
+            // input rows a chunk settles against the rows it owns (k1 = 3, s1 = 1: two rows above, two below the chunk's)
+            q.redundancy = (double)k.chunks * (k.rc * k.pool2.sh + 3) / (double)k.H;
+            q.n_levels = 2;
+            return BS_OK;
+        }
+    }
     // BatchNorm operations of the three lists, in order: the kernel stages their parameters in LDS
     {
         const EwOp *lists[3] = {k.pre, k.mid, k.post};

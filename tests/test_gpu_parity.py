@@ -802,10 +802,12 @@ def _check_nhwc(layers, x, res, dtype, label, **opts):
     for a, b in zip(idx, ref_idx):
         assert np.array_equal(a.cpu().numpy(), b), label
     names = [q["variant_name"] for q in info["sequences"]]
-    assert all(v in ("nhwc_stream", "nhwc_pool", "nhwc_tile") for v in names)
-    assert sum(2 if v == "nhwc_tile" else 1 for v in names) == info["n_steps"]
+    assert all(v in ("nhwc_stream", "nhwc_pool", "nhwc_tile", "nhwc_rows") for v in names)
+    assert sum(2 if v in ("nhwc_tile", "nhwc_rows") else 1 for v in names) == info["n_steps"]
     if opts.get("max_steps_per_sequence") == 1 or opts.get("breadth_first"):
-        assert "nhwc_tile" not in names
+        assert "nhwc_tile" not in names and "nhwc_rows" not in names
+    if opts.get("lane_exchange") == -1:
+        assert "nhwc_rows" not in names
     return info
 
 
@@ -898,12 +900,75 @@ def test_channels_last_two_pools_in_one_kernel(shape, dtype):
         x = wl.activation(shape, 178, dtype)
         x[:, :, ::3, ::2] = 0.0  # ties for the maximum and for its index
         res = [wl.activation(sh, 179 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
+        # lane_exchange = -1: the tile kernel also where the register kernel (below) would take the pair
         for opts in ({}, dict(tile_rows=1, tile_cols=1), dict(tile_rows=3, tile_cols=2, planes_per_group=vec),
                      dict(tile_rows=16, tile_cols=16, planes_per_group=vec)):
-            info = _check_nhwc(layers, x, res, dtype, f"tile/{name}{shape}", **opts)
+            info = _check_nhwc(layers, x, res, dtype, f"tile/{name}{shape}", lane_exchange=-1, **opts)
             assert [q["variant_name"] for q in info["sequences"]] == ["nhwc_tile"], name
         ran += 1
     assert ran >= 10
+
+
+def _nhwc_rows_stacks(c):
+    """Pairs of pooling steps the channels-last register kernel is compiled for (3 x 3 windows with padding 1, the
+    first with stride 1, the second a maximum with stride 1 or 2, no index output, lists of BatchNorm and ReLU
+    in the places the planner leaves them), and pairs it must leave to the tile kernel."""
+    mine = {
+        "halo_stress": [wl.bn_params(c, 180), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1), wl.bn_params(c, 181), wl.relu()],
+        "avg_max_s1": [wl.bn_params(c, 182), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 1, 1), wl.bn_params(c, 183), wl.relu()],
+        "avg_max_no_lists": [wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1)],
+        "avg_max_front_only": [wl.bn_params(c, 184), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1)],
+        "avg_max_behind_only": [wl.avgpool(3, 1, 1, True), wl.maxpool(3, 1, 1), wl.bn_params(c, 185), wl.relu()],
+        # lists in front of a maximum that never decrease run behind it: both end up behind the second pooling
+        "blocks2": [wl.maxpool(3, 1, 1), wl.bn_params(c, 186), wl.relu(), wl.maxpool(3, 1, 1), wl.bn_params(c, 187), wl.relu()],
+        "max_max_s2": [wl.maxpool(3, 1, 1), wl.maxpool(3, 2, 1), wl.bn_params(c, 188), wl.relu()],
+        "max_max_no_lists": [wl.maxpool(3, 1, 1), wl.maxpool(3, 2, 1)],
+    }
+    other = {
+        "in_range_count": [wl.bn_params(c, 180), wl.relu(), wl.avgpool(3, 1, 1, False), wl.maxpool(3, 2, 1)],
+        "with_indices": [wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1, True)],
+        "first_stride_2": [wl.avgpool(3, 2, 1, True), wl.maxpool(3, 1, 1)],
+        "average_last": [wl.maxpool(3, 1, 1), wl.avgpool(3, 2, 1, True)],
+        "other_list": [wl.leaky_relu(0.1), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1)],
+        "add_in_front": [wl.add(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1)],
+    }
+    return mine, other
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 13, 11), (1, 16, 9, 16), (2, 24, 12, 10), (1, 8, 57, 31), (3, 32, 7, 7), (1, 128, 6, 5),
+                                   (2, 64, 56, 56), (1, 8, 3, 64), (1, 8, 1, 1), (1, 16, 70, 2)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_channels_last_two_pools_in_registers(shape, dtype):
+    """The channels-last kernel whose lanes are the pixel columns of an image row (neighbouring columns by lane
+    shifts, no LDS; 16-bit storage) against the oracle: the planner's chunk length, one output row per chunk, a ragged last chunk,
+    the whole image as one chunk; images wider than a wave and the pairs it is not compiled for take the tile kernel."""
+    mine, other = _nhwc_rows_stacks(shape[1])
+    vec = 4 if dtype == "f32" else 8
+    for name, layers in mine.items():
+        x = wl.activation(shape, 189, dtype)
+        x[:, :, ::3, ::2] = 0.0
+        for rc in (0, 1, 3, 5, 1000):
+            info = _check_nhwc(layers, x, [], dtype, f"rows/{name}{shape}/rc{rc}", tile_rows=rc)
+            names = [q["variant_name"] for q in info["sequences"]]
+            if shape[1] % vec == 0 and dtype != "f32":  # compiled for 16-bit storage (float32 is faster through the tile kernel)
+                assert names == ["nhwc_rows"], name
+                q = info["sequences"][0]
+                assert q["lds_bytes"] == 0 and q["threads_per_group"] == 64 * min(8, shape[1] // vec)
+            else:
+                assert "nhwc_rows" not in names
+    for name, layers in other.items():
+        x = wl.activation(shape, 190, dtype)
+        res = [wl.activation(sh, 191 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
+        info = _check_nhwc(layers, x, res, dtype, f"rows-not/{name}{shape}")
+        assert "nhwc_rows" not in [q["variant_name"] for q in info["sequences"]], name
+
+
+def test_channels_last_register_kernel_needs_rows_that_fit_a_wave():
+    layers = [wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1)]
+    for w, want in ((64, True), (65, False)):
+        shape = (1, 8, 5, w)
+        info = _check_nhwc(layers, wl.activation(shape, 192, "bf16"), [], "bf16", f"rows/width{w}")
+        assert ("nhwc_rows" in [q["variant_name"] for q in info["sequences"]]) == want
 
 
 def _premax_stacks(c):

@@ -289,8 +289,20 @@ def test_channels_last_plans_take_one_or_two_steps_per_sequence():
             st = bs.Stack(layers, shape, dtype).plan(host_only=1, layout=bs.BS_LAYOUT_NHWC)
             info = st.info()
             names = [q["variant_name"] for q in info["sequences"]]
-            assert names == (["nhwc_tile"] if pools == 2 else ["nhwc_pool"] * pools if pools else ["nhwc_stream"])
+            # halo_stress (3 x 3 / 1 average, 3 x 3 / 2 maximum, 56 pixels per row) takes the register kernel with 16-bit storage
+            two = "nhwc_tile" if dtype == "f32" else "nhwc_rows"
+            assert names == ([two] if pools == 2 else ["nhwc_pool"] * pools if pools else ["nhwc_stream"])
             assert info["workspace_bytes"] == 0
+            for q in info["sequences"]:
+                if q["variant_name"] == "nhwc_rows":
+                    assert q["lds_bytes"] == 0 and q["threads_per_group"] == 64 * 8 and q["tile_rows"] == 14
+                    assert q["grid"] == shape[0] * (28 // 14) * (shape[1] // 8 // 8)
+            if pools == 2:  # without lane exchange: the tile kernel
+                st.close()
+                st = bs.Stack(layers, shape, dtype).plan(host_only=1, layout=bs.BS_LAYOUT_NHWC, lane_exchange=-1)
+                info = st.info()
+                names = [q["variant_name"] for q in info["sequences"]]
+                assert names == ["nhwc_tile"]
             for q in info["sequences"]:
                 if q["variant_name"] != "nhwc_tile":
                     continue
