@@ -118,8 +118,9 @@ BS_DEV void col_pool3(const float (&a)[VEC], const float (&b)[VEC], const float 
             s = s + left0(c[e]);
             s = s + c[e];
             s = s + right0(c[e]);
-            y[e] = round_store<DT>(s * inv_kk);
+            y[e] = s * inv_kk;
         }
+        round_store_all<DT, VEC>(y);
     }
 }
 
