@@ -190,12 +190,19 @@ typedef enum bs_layout {
  *                           skips the other channels in every pixel: bs_stack_run_strided
  *                           takes its batch stride, which must be H * W times the larger
  *                           tensor's channel count.  Index outputs hold the same values
- *                           (ih * W + iw) in channels-last order.
+ *                           (ih * W + iw) in channels-last order.  With 16-bit storage a pair of
+ *                           3 x 3 steps with padding 1 -- the first with stride 1, the second a
+ *                           maximum with stride 1 or 2, no index output, images at most 64 pixels
+ *                           wide -- runs as one BS_VARIANT_NHWC_ROWS sequence instead (rows in
+ *                           registers, no LDS); tile_rows is then the number of output rows per
+ *                           work-group.
  *   lane_exchange           sliding-window (BS_VARIANT_POOL_ROWS) sequences on planes whose rows fit one
  *                           wave as 128-bit column blocks (at most 64 of them): 0 = the lanes pass
  *                           their edge columns to their neighbours inside the wave (each input
  *                           element is loaded and computed once); -1 = every lane loads and
  *                           recomputes the columns next to its block itself, as for wider planes.
+ *                           Channels-last plans: -1 = no BS_VARIANT_NHWC_ROWS sequences (the pairs
+ *                           they would take run as BS_VARIANT_NHWC_TILE).
  */
 typedef struct bs_plan_options {
     uint64_t max_lds_bytes;
