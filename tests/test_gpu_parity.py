@@ -1022,13 +1022,18 @@ def test_channels_last_channel_slices(shape, dtype):
               "avg3s1": [wl.bn_params(c, 164), wl.relu(), wl.avgpool(3, 1, 1)],
               "any": [wl.relu(), wl.maxpool((2, 3), (1, 2), (1, 1), True)],
               "head": [wl.bn_params(c, 165), wl.relu(), wl.avgpool((h, w), (h, w), 0)],
-              "two_pools": [wl.bn_params(c, 166), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1, True), wl.relu()]}
+              "two_pools": [wl.bn_params(c, 166), wl.relu(), wl.avgpool(3, 1, 1), wl.maxpool(3, 2, 1, True), wl.relu()],
+              # without the index output: the register kernel with 16-bit storage
+              "two_pools_in_registers": [wl.bn_params(c, 166), wl.relu(), wl.avgpool(3, 1, 1, True), wl.maxpool(3, 2, 1),
+                                         wl.bn_params(c, 159), wl.relu()]}
     for name, layers in stacks.items():
         print(f"[parity] nhwc-slice/{name}{shape} {dtype}", flush=True)
         x = wl.activation(shape, 167, dtype)
         res = [wl.activation(sh, 168 + i, dtype) for i, sh in enumerate(wl.residual_shapes(layers, shape))]
         ref, ref_idx, _ = bf.run_stack(layers, x, res, dtype)
         st = bs.Stack(layers, shape, dtype).plan(layout=bs.BS_LAYOUT_NHWC)
+        if name == "two_pools_in_registers" and dtype != "f32":
+            assert [q["variant_name"] for q in st.info()["sequences"]] == ["nhwc_rows"]
         big_in = torch.full((n, c + 16, h, w), float("nan"), dtype=td, device="cuda").contiguous(memory_format=cl)
         big_in[:, 8:8 + c] = _dev(x, dtype)
         guard = 4321.0
