@@ -80,10 +80,15 @@ constexpr int K_XROWS2_VEC32 = 4, K_XROWS2_VEC16 = 8;  // two pooling operations
 // Output rows per lane in pool_xrows2_kernel.  Longer chunks recompute less, but the kernel is bound by
 // instruction issue and wants many waves: measured best on 56 x 56 planes.
 constexpr int K_XROWS2_RC32 = 2, K_XROWS2_RC16 = 4;
-constexpr int K_NHWC_ROWS_WAVES = 8;  // channel vectors (waves) per work-group of nhwc_rows2_kernel: the 128 bytes of one cache line
-// Output rows per chunk of that kernel.  Measured on MI355X (halo_stress, 28 output rows, bfloat16 / binary16, us): 2 -> 89 / 65,
-// 4 -> 75 / 59, 7 -> 70 / 56, 14 -> 66 / 55.
-constexpr int K_NHWC_ROWS_RC = 14;
+// Channel vectors (waves) per work-group of nhwc_rows2_kernel and output rows per chunk.  Measured on MI355X (halo_stress
+// channels-last, 28 output rows, bfloat16 / binary16, us) -- 8 waves (the 128 bytes of one cache line): 4 rows 74 / 59,
+// 7 rows 68 / 56, 14 rows 64 / 55; 4 waves: 60 / 56, 57 / 55, 64 / 55; 2 waves: 87 / 88, 80 / 81, 82 / 78.  With eight waves and the
+// bfloat16 instance's 168 registers (three waves per SIMD) only one work-group fits a compute unit.
+#if !defined(BS_NHWC_ROWS_WAVES)
+#define BS_NHWC_ROWS_WAVES 4
+#endif
+constexpr int K_NHWC_ROWS_WAVES = BS_NHWC_ROWS_WAVES;
+constexpr int K_NHWC_ROWS_RC = 7;
 constexpr int K_LDS_RB = 2;       // consecutive rows one lane pools per strip in the specialised LDS kernels
 constexpr int K_DIRECT_U = 1;     // units per lane in pool_direct_kernel (2 measured 1..2 % slower on the VGG stacks)
 constexpr int K_PLANE_WALK_CELLS = 16;  // whole-plane pooling: planes up to this many cells are walked in global

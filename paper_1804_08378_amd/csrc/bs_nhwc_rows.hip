@@ -10,8 +10,8 @@
 // LDS, nothing is synchronised, every input element is loaded once per chunk that needs it.
 //
 // Memory: a lane reads the 16 bytes of its channel vector, C * element size bytes from its neighbour's;
-// the cache lines of a pixel are shared by the waves of the work-group (eight: one 128-byte line of a
-// pixel is eight channel vectors with either element size), which request the same rows at the same time (measured on MI355X: this mapping streams 205 MB at 6.1 TB/s from the last-level
+// the cache lines of a pixel are shared by the waves of the work-group (four: half a 128-byte line of a
+// pixel; eight measured slower, see K_NHWC_ROWS_WAVES), which request the same rows at the same time (measured on MI355X: this mapping streams 205 MB at 6.1 TB/s from the last-level
 // cache against 8.0 TB/s for contiguous lanes -- above what HBM delivers either way).
 //
 // Compiled for 16-bit storage and the 3 x 3 windows with padding 1 the benchmark's stacks use: first pooling with
@@ -325,8 +325,8 @@ bool lists_compiled(const NhwcTile2K &k)
 // Is this pair of pooling steps (lists already in the places plan_nhwc_tile2 gives them) one the kernel is compiled for?
 bool nhwc_rows2_supported(const NhwcTile2K &k, int32_t dtype)
 {
-    // 16-bit storage only.  Measured on MI355X (halo_stress, us): bfloat16 66 against the tile kernel's 86, binary16 55
-    // against 83, float32 91 against 77 -- with float32 a pixel's channels are two cache lines, read by two work-groups.
+    // 16-bit storage only.  Measured on MI355X (halo_stress, us): bfloat16 57 against the tile kernel's 86, binary16 55
+    // against 83, float32 (eight waves per work-group) 91 against 77.
     if (dtype != BS_BF16 && dtype != BS_F16) return false;
     const PoolK &a = k.pool1, &b = k.pool2;
     auto is3p1 = [](const PoolK &p) { return p.kh == 3 && p.kw == 3 && p.ph == 1 && p.pw == 1 && p.sh == p.sw; };

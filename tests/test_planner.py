@@ -295,8 +295,8 @@ def test_channels_last_plans_take_one_or_two_steps_per_sequence():
             assert info["workspace_bytes"] == 0
             for q in info["sequences"]:
                 if q["variant_name"] == "nhwc_rows":
-                    assert q["lds_bytes"] == 0 and q["threads_per_group"] == 64 * 8 and q["tile_rows"] == 14
-                    assert q["grid"] == shape[0] * (28 // 14) * (shape[1] // 8 // 8)
+                    assert q["lds_bytes"] == 0 and q["threads_per_group"] == 64 * 4 and q["tile_rows"] == 7
+                    assert q["grid"] == shape[0] * (28 // 7) * (shape[1] // 8 // 4)
             if pools == 2:  # without lane exchange: the tile kernel
                 st.close()
                 st = bs.Stack(layers, shape, dtype).plan(host_only=1, layout=bs.BS_LAYOUT_NHWC, lane_exchange=-1)
