@@ -11,8 +11,8 @@
 //
 // Memory: a lane reads the 16 bytes of its channel vector, C * element size bytes from its neighbour's;
 // the cache lines of a pixel are shared by the waves of the work-group (four: half a 128-byte line of a
-// pixel; eight measured slower, see K_NHWC_ROWS_WAVES), which request the same rows at the same time (measured on MI355X: this mapping streams 205 MB at 6.1 TB/s from the last-level
-// cache against 8.0 TB/s for contiguous lanes -- above what HBM delivers either way).
+// pixel; eight measured slower, see K_NHWC_ROWS_WAVES), which request the same rows at the same time.  Measured on
+// MI355X, the rate of these 16-byte lane requests is what bounds the kernel (about 2.3 TB/s of algorithmic bytes).
 //
 // Compiled for 16-bit storage and the 3 x 3 windows with padding 1 the benchmark's stacks use: first pooling with
 // stride 1 (average or maximum), second pooling a maximum with stride 1 or 2, no index output,
