@@ -580,6 +580,9 @@ def main():
                     help="also measure what streaming access patterns without arithmetic reach (bs_probe_stream)")
     ap.add_argument("--launch", nargs=2, metavar=("SPEC", "N"),
                     help="only launch one configuration N times (for rocprofv3): SPEC = NAME:DTYPE[:key=value,...]")
+    ap.add_argument("--time", nargs=2, metavar=("SPEC", "N"), dest="time_one",
+                    help="time the fused plan of one configuration: N single launches between event pairs over rotating "
+                         "inputs; SPEC as for --launch (forward plans; plan options and indices=1).  One JSON line.")
     ap.add_argument("--probe", type=int, default=0, metavar="N",
                     help="counter probe for rocprofv3 --pmc: N launches of a plain copy of known size, "
                          "then N launches of each VGG stack; no timing, no JSON")
@@ -601,6 +604,18 @@ def main():
 
     if args.launch:
         launch_only(args.launch[0], int(args.launch[1]))
+        return
+
+    if args.time_one:
+        parts = args.time_one[0].split(":")
+        opts = {k: int(v) for k, v in (kv.split("=") for kv in parts[2].split(","))} if len(parts) > 2 and parts[2] else {}
+        sb = StackBench(parts[0], parts[1], indices=bool(opts.pop("indices", 0)), **opts)
+        _, per, mins = time_steps([sb], "fused", int(args.time_one[1]), 3)
+        q = sb.info["sequences"]
+        print(json.dumps({"config": parts[0], "dtype": parts[1], "options": opts, "launches": int(args.time_one[1]),
+                          "us_mean": round(per[parts[0]] * 1e3, 1), "us_min": round(mins[parts[0]] * 1e3, 1),
+                          "GBps": round(sb.bytes / (per[parts[0]] * 1e-3) / 1e9), "variants": [x["variant_name"] for x in q],
+                          "tile_rows": [x["tile_rows"] for x in q], "work_groups": [x["grid"] for x in q]}))
         return
 
     if args.probe:
