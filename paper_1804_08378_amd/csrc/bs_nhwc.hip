@@ -416,6 +416,8 @@ int32_t nhwc_plane_group(int64_t hw, int32_t vec, const PoolK &p, int32_t H, int
 // MI355X: sharing cells between the outputs of a block pays for stride 1 (3x3/1: 2 x 2 outputs
 // from 4 x 4 cells with float32 vectors, 2 x 1 from 4 x 3 with the twice as long 16-bit
 // vectors), not for stride 2 (3x3/2: 1 x 2 was 20..60 % slower than 1 x 1: registers).
+// The 16-bit 3x3/1 instance with its 2 x 1 block holds 241 registers (two waves per SIMD); with a 1 x 1 block it holds
+// fewer and is slower all the same (halo_stress channels-last step by step, both steps: 162 -> 180 us).
 // The planner sizes the grid with it, the launcher picks the instance.
 void nhwc_block(const PoolK &p, int32_t vec, int32_t dtype, int32_t &ohb, int32_t &owb)
 {
