@@ -7,7 +7,8 @@
 // window needs from the columns left and right of it are the neighbouring lanes' values, read through
 // data-parallel-primitive operands (the compiler folds a lane shift into the add that uses it; a
 // maximum takes one v_mov_b32 with the padding value as its "old" operand).  Nothing goes through
-// LDS, nothing is synchronised, every input element is loaded once per chunk that needs it.
+// LDS; the waves of a work-group meet at a barrier after every row request, which only keeps them
+// on the same rows (row_sync below); every input element is loaded once per chunk that needs it.
 //
 // Memory: a lane reads the 16 bytes of its channel vector, C * element size bytes from its neighbour's;
 // the cache lines of a pixel are shared by the waves of the work-group (four: half a 128-byte line of a
