@@ -155,7 +155,8 @@ typedef enum bs_layout {
  * Planner options; NULL or all-zero = automatic.
  *   max_lds_bytes           on-chip budget per work-group (Section 4.1 "resource limit")
  *   max_steps_per_sequence  the strategy knob of Section 5.1 (1, 5, 0 = unrestricted)
- *   threads_per_group       64..1024, multiple of 64 (0 = 256)
+ *   threads_per_group       64..512, multiple of 64 (0 = 256); the pooling kernels take at most 256, the
+ *                           channels-last two-pool kernels have work-groups of their own size
  *   num_cus                 compute units to size grids for (0 = query the current device)
  *   breadth_first           != 0: one sequence per layer, i.e. the layer-by-layer execution
  *                           of Figure 2 with every intermediate in the workspace

@@ -928,7 +928,7 @@ static void plan_exchange(Sequence &q, K &k, int64_t planes, int32_t rc, int32_t
     k.div_cbs = make_fastdiv((uint32_t)k.cbs);
     k.div_chunks = make_fastdiv((uint32_t)k.chunks);
     k.div_c = make_fastdiv((uint32_t)k.C);
-    q.threads = 256;
+    q.threads = std::max(64, std::min(q.threads, 256));  // whole waves; the kernels have no barrier, any number of waves works
     const int64_t per_group = (int64_t)k.spw * (q.threads / 64);
     q.grid = ((int64_t)k.units + per_group - 1) / per_group;
 }

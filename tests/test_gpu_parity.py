@@ -299,6 +299,10 @@ def test_pool_rows_kernel(shape, dtype):
                 info = check(layers, x, [], dtype, f"rows/{name}{shape}/rc{rc}/x{exchange}", tile_rows=rc,
                              lane_exchange=exchange)
                 assert info["sequences"][0]["variant_name"] == "pool_rows", name
+        # work-groups of one and of three waves (the kernels have no barrier: any number of whole waves)
+        for threads in (64, 192):
+            info = check(layers, x, [], dtype, f"rows/{name}{shape}/threads{threads}", threads_per_group=threads)
+            assert info["sequences"][0]["threads_per_group"] == threads, name
         # the same stack through the LDS kernels agrees as well
         info = check(layers, x, [], dtype, f"rows/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
         assert info["sequences"][0]["variant_name"] == "lds_tile"
@@ -330,6 +334,10 @@ def test_pool_rows2_kernel(shape, dtype):
                              force_variant=bs.BS_VARIANT_POOL_ROWS, lane_exchange=exchange)
                 assert info["n_sequences"] == 1, name
                 assert info["sequences"][0]["variant_name"] == "pool_rows", name
+        for threads in (64, 192):
+            info = check(layers, x, [], dtype, f"rows2/{name}{shape}/threads{threads}", threads_per_group=threads,
+                         force_variant=bs.BS_VARIANT_POOL_ROWS)
+            assert info["sequences"][0]["threads_per_group"] == threads, name
         info = check(layers, x, [], dtype, f"rows2/{name}{shape}/lds", force_variant=bs.BS_VARIANT_LDS_TILE)
         assert [q["variant_name"] for q in info["sequences"]] == ["lds_tile"] * info["n_sequences"]
 

@@ -353,3 +353,20 @@ def test_channels_last_plans_take_one_or_two_steps_per_sequence():
         assert bs.bs_stack_check_buffers(h, 4096, 8 * 8 * 8, None, 4096 + 16, 8 * 8 * 8, None, 0, 0) == 12
     finally:
         bs.bs_stack_destroy(h)
+
+
+def test_threads_per_group_is_honoured_by_the_register_kernels():
+    """The sliding-row kernels have no barrier, so a work-group may be any number of whole waves:
+    the plan option changes the work-group size and the grid, not the work per wave."""
+    for name, dtype in (("halo_stress", "f32"), ("halo_stress", "bf16"), ("resnet_stem", "f16")):
+        layers, shape = wl.build(name)[:2]
+        base = plan(layers, shape, dtype)["sequences"][0]
+        assert base["variant_name"] == "pool_rows" and base["threads_per_group"] == 256
+        for threads in (64, 128, 192):
+            q = plan(layers, shape, dtype, threads_per_group=threads)["sequences"][0]
+            assert q["variant_name"] == "pool_rows" and q["threads_per_group"] == threads
+            assert q["tile_rows"] == base["tile_rows"]
+            waves = base["grid"] * 4
+            assert -(-waves // (threads // 64)) - 1 <= q["grid"] <= -(-waves // (threads // 64))
+        q = plan(layers, shape, dtype, threads_per_group=512)["sequences"][0]
+        assert q["threads_per_group"] == 256 and q["grid"] == base["grid"]
