@@ -556,7 +556,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also report every benchmark configuration (stderr)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-batch", type=int, default=32)
-    ap.add_argument("--cpu-passes", type=int, default=10)
+    ap.add_argument("--cpu-passes", type=int, default=25,
+                    help="passes of the CPU oracle over the workload (25: about 17 core-seconds on 16 threads)")
     ap.add_argument("--no-baseline", action="store_true",
                     help="skip the layer-by-layer HIP plan (its pooling layer runs the same kernel symbol "
                          "as the fused stack, which would mix the two in a rocprofv3 --stats summary)")
