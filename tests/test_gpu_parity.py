@@ -944,7 +944,8 @@ def _nhwc_rows_stacks(c):
 
 
 @pytest.mark.parametrize("shape", [(2, 8, 13, 11), (1, 16, 9, 16), (2, 24, 12, 10), (1, 8, 57, 31), (3, 32, 7, 7), (1, 128, 6, 5),
-                                   (2, 64, 56, 56), (1, 8, 3, 64), (1, 8, 1, 1), (1, 16, 70, 2)])
+                                   (2, 64, 56, 56), (1, 8, 3, 64), (1, 8, 1, 1), (1, 16, 70, 2),
+                                   (8, 16, 9, 10), (16, 40, 17, 6), (24, 8, 5, 33)])  # batches of 8 k: work-groups ordered by XCD
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_channels_last_two_pools_in_registers(shape, dtype):
     """The channels-last kernel whose lanes are the pixel columns of an image row (neighbouring columns by lane
